@@ -1,0 +1,164 @@
+/* aemodel.h — C boundary of the MI355X noisy-channel autoencoder library.
+ *
+ * The library runs the batched forward (and backward) pass of a learned
+ * transmission pipeline: a conv / fully-connected encoder with batch-norm,
+ * ReLU and 2x2 max-pooling, per-sample power normalisation, additive white
+ * Gaussian noise from a Philox4x32-10 counter-based generator at a requested
+ * SNR, and a nearest-upsampling conv / fc decoder, plus the MSE loss and the
+ * Monte-Carlo bookkeeping (message bits, error counts) used for error-rate
+ * estimation.  The pipeline and its five workloads are the ones the project's
+ * contract states (the attached paper's text does not define them); each entry
+ * point below therefore states the definition it implements in full.
+ *
+ * Conventions common to all calls
+ *  - Every tensor pointer is a DEVICE pointer owned by the caller unless the
+ *    argument is documented as host memory.  The library never frees or keeps a
+ *    caller pointer beyond the call's enqueued work.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Calls only enqueue work; they do not synchronise.
+ *  - Return value: AE_OK (0) or a negative ae_status.  No call aborts or throws;
+ *    model_last_error() returns a thread-local message for the last failure.
+ *  - dtype AE_F32: tensors are IEEE binary32.  dtype AE_BF16: x, y, dy, targets
+ *    and every stored activation are bfloat16 (round-to-nearest-even), all
+ *    accumulation / statistics / noise / loss arithmetic is binary32, and the
+ *    parameter blob and the gradient blob are binary32 in both modes.
+ *  - Image tensors at the boundary are NCHW, contiguous.
+ *  - One model handle must not be used from two threads or two streams at once.
+ */
+#ifndef AEMODEL_H
+#define AEMODEL_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ae_model ae_model; /* opaque, library-owned */
+
+enum ae_status {
+  AE_OK = 0,
+  AE_EINVAL = -1, /* null pointer, bad size or bad enum value          */
+  AE_ESPEC = -2,  /* layer spec does not parse or uses an unsupported sequence */
+  AE_ESHAPE = -3, /* shapes in the spec do not fit together             */
+  AE_ESTATE = -4, /* call order violated (backward before forward)      */
+  AE_ENOMEM = -5, /* device allocation failed                           */
+  AE_EHIP = -6    /* a HIP runtime call failed (no device, launch error) */
+};
+
+enum ae_dtype { AE_F32 = 0, AE_BF16 = 1 };
+
+/* ---- layer spec ----------------------------------------------------------
+ * Comma-separated tokens; the first is the per-sample input shape.
+ *   in:CxHxW      input shape
+ *   conv3:N       3x3 cross-correlation, stride 1, zero pad 1, N output channels, + bias
+ *   conv1:N       1x1 convolution, + bias
+ *   fc:N          fully connected layer on a flattened (Cx1x1) tensor, + bias
+ *   bn            batch normalisation per channel over (batch, H, W), eps = 1e-5,
+ *                 biased variance (bn_mode 0: batch statistics; 1: stored statistics)
+ *   relu | sigmoid
+ *   pool2         2x2 max-pool, stride 2 (H and W must be even)
+ *   up2           nearest-neighbour upsampling x2 (must be followed by a conv)
+ *   flatten       CxHxW -> (C*H*W)x1x1 in (c,h,w) order
+ *   reshape:CxHxW inverse of flatten
+ *   pnorm         scale each sample's whole tensor to unit mean power: x = z / sqrt(mean z^2)
+ *                 (x = 0 when the sample is all zero)
+ *   awgn          y = x + sigma * g, g ~ N(0,1) from Philox, sigma^2 = 10^(-snr_db/10)
+ * Accepted sequences: [up2] conv|fc [bn] [relu|sigmoid] [pool2]; flatten; reshape;
+ * pnorm; awgn; pnorm,awgn.  Anything else is AE_ESPEC.
+ *
+ * Parameter blob (binary32, caller-owned), in spec order:
+ *   conv: W[C_out][C_in][k][k] then b[C_out];  fc: W[out][in] then b[out];
+ *   bn: gamma[C], beta[C] (bn_mode 1: then mean[C], var[C]).
+ * The gradient blob has the same layout (stored-statistics slots receive 0).
+ */
+
+/* Parse `layer_spec` and report sizes without touching the GPU (host-only).
+ * Any output pointer may be NULL.  workspace_bytes is what model_create would
+ * allocate on the device for this batch and dtype. */
+int model_describe(const char* layer_spec, int batch, int dtype, int bn_mode, int64_t* n_params,
+                   int64_t in_chw[3], int64_t out_chw[3], int64_t* latent_n, int64_t* workspace_bytes);
+
+/* Build a model for a fixed batch size: parses the spec, infers shapes, chooses
+ * a kernel per layer and allocates the model-owned device workspace (saved
+ * activations, packed weights, batch-norm partial sums, gradient staging) on the
+ * current device.  *out receives the handle; free it with model_destroy. */
+int model_create(const char* layer_spec, int batch, int dtype, int bn_mode, ae_model** out);
+void model_destroy(ae_model* m);
+
+int model_param_count(const ae_model* m, int64_t* n_params);
+int model_io_shape(const ae_model* m, int64_t in_chw[3], int64_t out_chw[3], int64_t* latent_n);
+
+/* Global index of sample 0 of the next model_forward (default 0).  The noise of
+ * a sample depends only on (seed, global sample index, element index), so a
+ * Monte-Carlo run split into launches gives the same noise as one big launch. */
+int model_set_sample_offset(ae_model* m, uint64_t first_sample);
+
+/* Forward pass of the whole pipeline on one batch.
+ *   params : device, binary32[n_params]          x : device, [batch][C][H][W] (model dtype)
+ *   y      : device, [batch][C_out][H_out][W_out] (model dtype), written
+ * Noise: element i (in (c,h,w) order) of the tensor entering `awgn`, sample with
+ * global index g, receives sigma * N where sigma = (float)10^(-snr_db/20) and N is
+ * deviate (i&1) of word pair (i&3)>>1 of Philox4x32-10(counter = (g_lo, g_hi, i>>2, 0),
+ * key = (seed_lo, seed_hi)), mapped to a normal deviate by the fixed binary32
+ * Box-Muller sequence documented with model_noise.  Activations are kept inside
+ * the model for a following model_backward. */
+int model_forward(ae_model* m, const void* params, const void* x, float snr_db, uint64_t seed, void* y,
+                  void* stream);
+
+/* Backward pass through the graph of the immediately preceding model_forward on
+ * the same handle (AE_ESTATE otherwise), with the same params and x.
+ *   dy    : device, gradient of a scalar loss w.r.t. y, same shape/dtype as y
+ *   grads : device, binary32[n_params], overwritten with d loss / d params
+ * Definitions: conv/fc adjoints; batch-norm with batch statistics
+ * dx = gamma*invstd*(dy - mean(dy) - xhat*mean(dy*xhat)); max-pool routes to the
+ * first maximum in scan order (0,0),(0,1),(1,0),(1,1); upsample sums its 2x2
+ * copies; pnorm dz = (g - x*mean(g.x))/r; the noise is additive (identity);
+ * ReLU derivative is 0 for inputs <= 0; sigmoid dy*y*(1-y). */
+int model_backward(ae_model* m, const void* params, const void* x, const void* dy, void* grads, void* stream);
+
+/* Mean squared error over all n_elem elements: *loss_dev = mean((y-t)^2) (device,
+ * binary32, overwritten); if dy is non-NULL it receives 2*(y-t)/n_elem in `dtype`. */
+int model_loss_mse(const void* y, const void* target, int64_t n_elem, int dtype, float* loss_dev, void* dy,
+                   void* stream);
+
+/* Standard-normal tensor out[batch][n] (device, binary32) exactly as the forward
+ * pass draws it (before scaling by sigma).  Words (w0,w1) -> (g0,g1):
+ *   u = fma(float(w0), 2^-32, 2^-33); ln u by range reduction to [sqrt(1/2), sqrt 2)
+ *   and a fixed degree-8 polynomial; rho = sqrt(-2 ln u); the angle is the quadrant
+ *   (top two bits of w1) plus a 24-bit fraction of a quarter turn, evaluated with
+ *   fixed polynomials for sin and cos of (pi/2)*r on [0,1/2]; g0 = rho*cos, g1 = rho*sin.
+ * Every step is one correctly rounded binary32 operation, so the tensor is
+ * reproducible bit for bit on any IEEE machine. */
+int model_noise(uint64_t seed, uint64_t first_sample, int64_t batch, int64_t n, float* out, void* stream);
+
+/* Stand-alone fused power normalisation + AWGN on z[batch][n] (contiguous, `dtype`),
+ * the same kernel the forward pass uses for a flattened latent.  y may alias z. */
+int model_pnorm_awgn(const void* z, void* y, int64_t batch, int64_t n, int dtype, float snr_db, uint64_t seed,
+                     uint64_t first_sample, void* stream);
+
+/* Monte-Carlo message source: x_pm1[batch][k] (device, binary32) = +1 where bit j
+ * of the sample's message is set, else -1.  Bit j of global sample g is bit (j&31)
+ * of word (j>>5)&3 of Philox4x32-10(counter = (g_lo, g_hi, j>>7, 1), key = seed). */
+int model_gen_bits(uint64_t seed, uint64_t first_sample, int64_t batch, int k, float* x_pm1, void* stream);
+
+/* Hard decisions at 1/2 on y[batch][k] (device, binary32) against the sent symbols:
+ * adds the number of wrong bits to *bit_err and the number of blocks with at least
+ * one wrong bit to *blk_err (device, 64-bit counters the caller zeroes once). */
+int model_count_errors(const float* y, const float* x_pm1, int64_t batch, int k, uint64_t* bit_err,
+                       uint64_t* blk_err, void* stream);
+
+/* Introspection for tests.  The pipeline is executed as fused steps; step s has
+ * one saved output tensor.  model_step_info reports, for step s, the index of the
+ * LAST spec token (0-based, not counting "in:") folded into it and its output
+ * shape; model_get_activation writes that saved output as binary32 NCHW. */
+int model_num_steps(const ae_model* m, int* n_steps);
+int model_step_info(const ae_model* m, int step, int* last_token, int64_t chw[3]);
+int model_get_activation(ae_model* m, int step, float* out_nchw, void* stream);
+
+const char* model_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AEMODEL_H */

@@ -197,6 +197,15 @@ struct Op {
 struct Net {
   int batch = 0;
   int bn_mode = 0;  // 0 = batch statistics, 1 = stored (running) statistics
+  // Storage-format emulation for the bfloat16 workloads ("bf16 storage, fp32 accumulate").
+  // When set, every tensor the format stores is rounded to bfloat16 (nearest, ties to
+  // even): the output of each conv / fc (bias included), the output of each maximal run
+  // of bn / relu / sigmoid / pool2 ops, and the output of the pnorm / awgn run.  The
+  // arithmetic in between stays in double.  This puts the discrete decisions that
+  // depend on stored values (ReLU masks, max-pool winners) in the precision the format
+  // prescribes, which is what a gradient comparison needs; without it the oracle is the
+  // plain real-number definition.
+  int store_bf16 = 0;
   int c0 = 0, h0 = 0, w0 = 0;
   std::vector<Op> ops;
   int64_t n_params = 0;
@@ -287,6 +296,27 @@ bool parse_spec(const char* spec, int batch, int bn_mode, Net* net) {
   }
   net->n_params = off;
   return true;
+}
+
+// nearest bfloat16 (8 significant bits), ties to even; exact zero, inf and nan pass through
+inline double round_bf16(double v) {
+  if (v == 0.0 || !std::isfinite(v)) return v;
+  int e;
+  double m = std::frexp(v, &e);               // |m| in [0.5, 1)
+  return std::ldexp(std::nearbyint(m * 256.0), e - 8);
+}
+
+inline bool is_pointwise_chain_op(OpKind k) { return k == OP_BN || k == OP_RELU || k == OP_SIGMOID || k == OP_POOL2; }
+
+// does the storage format materialise the output of op i?
+bool stored_output(const Net& net, size_t i) {
+  const OpKind k = net.ops[i].kind;
+  const bool has_next = i + 1 < net.ops.size();
+  const OpKind nk = has_next ? net.ops[i + 1].kind : OP_CONV;
+  if (k == OP_CONV || k == OP_FC || k == OP_AWGN) return true;
+  if (is_pointwise_chain_op(k)) return !(has_next && is_pointwise_chain_op(nk));
+  if (k == OP_PNORM) return !(has_next && nk == OP_AWGN);
+  return false;  // up2 / flatten / reshape copy already-rounded values
 }
 
 inline int64_t vol(const Op& o, bool out) {
@@ -653,8 +683,9 @@ void oracle_count_errors(const double* y, const float* x_pm1, int64_t batch, int
   *blk_err = ke;
 }
 
-void* oracle_create(const char* spec, int batch, int bn_mode) {
+void* oracle_create(const char* spec, int batch, int bn_mode, int store_bf16) {
   Net* net = new Net();
+  net->store_bf16 = store_bf16;
   if (batch <= 0 || !parse_spec(spec, batch, bn_mode, net)) {
     delete net;
     return nullptr;
@@ -715,6 +746,8 @@ int oracle_forward(void* h, const float* params, const float* x, float snr_db, u
       case OP_PNORM: pnorm_forward(B, vol(o, false), in, out, net->pn_r); break;
       case OP_AWGN: awgn_forward(B, vol(o, false), snr_db, seed, first_sample, in, out); break;
     }
+    if (net->store_bf16 && stored_output(*net, i))
+      for (size_t j = 0; j < out.size(); ++j) out[j] = round_bf16(out[j]);
   }
   net->have_forward = true;
   if (y) std::memcpy(y, net->acts[nops].data(), net->acts[nops].size() * sizeof(double));
@@ -755,9 +788,12 @@ int oracle_backward(void* h, const float* params, const double* dy, double* grad
         gprev.resize(g.size());
         for (size_t j = 0; j < g.size(); ++j) gprev[j] = in[j] > 0.0 ? g[j] : 0.0;
         break;
-      case OP_SIGMOID:
+      case OP_SIGMOID:  // s'(x) = s(x)(1-s(x)), evaluated from the op's input (the stored output may be rounded)
         gprev.resize(g.size());
-        for (size_t j = 0; j < g.size(); ++j) gprev[j] = g[j] * out[j] * (1.0 - out[j]);
+        for (size_t j = 0; j < g.size(); ++j) {
+          double sg = 1.0 / (1.0 + std::exp(-in[j]));
+          gprev[j] = g[j] * sg * (1.0 - sg);
+        }
         break;
       case OP_POOL2: pool_backward(o, B, in, g, gprev); break;
       case OP_UP2: up_backward(o, B, g, gprev); break;

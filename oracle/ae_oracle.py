@@ -39,7 +39,7 @@ def lib():
         L.oracle_sigma.restype = C.c_float
         L.oracle_gen_bits.argtypes = [C.c_uint64, C.c_uint64, C.c_int64, C.c_int, f32p]
         L.oracle_count_errors.argtypes = [f64p, f32p, C.c_int64, C.c_int, u64p, u64p]
-        L.oracle_create.argtypes = [C.c_char_p, C.c_int, C.c_int]
+        L.oracle_create.argtypes = [C.c_char_p, C.c_int, C.c_int, C.c_int]
         L.oracle_create.restype = C.c_void_p
         L.oracle_destroy.argtypes = [C.c_void_p]
         L.oracle_param_count.argtypes = [C.c_void_p]
@@ -131,8 +131,10 @@ OP_KINDS = ["conv", "bn", "relu", "sigmoid", "pool2", "up2", "flatten", "fc", "r
 class Net:
     """One parsed network; forward() keeps every activation for backward() and for the tests."""
 
-    def __init__(self, spec, batch, bn_mode=0):
-        self._h = lib().oracle_create(spec.encode(), batch, bn_mode)
+    def __init__(self, spec, batch, bn_mode=0, store_bf16=False):
+        """store_bf16=True emulates the bfloat16 storage format: every tensor that format
+        stores is rounded to bfloat16 (see the comment on Net::store_bf16 in ae_oracle.cpp)."""
+        self._h = lib().oracle_create(spec.encode(), batch, bn_mode, 1 if store_bf16 else 0)
         if not self._h:
             raise ValueError("oracle: bad layer spec or batch: %r" % spec)
         self.batch = batch

@@ -1,0 +1,189 @@
+"""ctypes binding of libaemodel.so: argument marshalling only.
+
+Every function has the name and argument order of the C entry point it calls
+(include/aemodel.h).  Tensors are torch tensors on the GPU; the binding passes
+their data pointers and the current HIP stream and checks the status code.
+Nothing is computed here and there is no fallback: if the library is missing the
+import fails.
+"""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libaemodel.so")
+
+AE_F32, AE_BF16 = 0, 1
+DTYPES = {"f32": AE_F32, "bf16": AE_BF16}
+TORCH_DTYPE = {AE_F32: torch.float32, AE_BF16: torch.bfloat16}
+
+SYMBOLS = [
+    "model_describe", "model_create", "model_destroy", "model_param_count", "model_io_shape",
+    "model_set_sample_offset", "model_forward", "model_backward", "model_loss_mse", "model_noise",
+    "model_pnorm_awgn", "model_gen_bits", "model_count_errors", "model_num_steps", "model_step_info",
+    "model_get_activation", "model_last_error",
+]
+
+
+class AeError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("aemodel error %d: %s" % (code, msg))
+        self.code = code
+
+
+def _load():
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError("libaemodel.so is not built: run `python -m paper_2602_17681_amd.build` "
+                          "(the HIP library is the only implementation; there is no fallback)")
+    L = C.CDLL(_LIB_PATH)
+    vp, i64p = C.c_void_p, C.POINTER(C.c_int64)
+    L.model_describe.argtypes = [C.c_char_p, C.c_int, C.c_int, C.c_int, i64p, i64p, i64p, i64p, i64p]
+    L.model_create.argtypes = [C.c_char_p, C.c_int, C.c_int, C.c_int, C.POINTER(vp)]
+    L.model_destroy.argtypes = [vp]
+    L.model_destroy.restype = None
+    L.model_param_count.argtypes = [vp, i64p]
+    L.model_io_shape.argtypes = [vp, i64p, i64p, i64p]
+    L.model_set_sample_offset.argtypes = [vp, C.c_uint64]
+    L.model_forward.argtypes = [vp, vp, vp, C.c_float, C.c_uint64, vp, vp]
+    L.model_backward.argtypes = [vp, vp, vp, vp, vp, vp]
+    L.model_loss_mse.argtypes = [vp, vp, C.c_int64, C.c_int, vp, vp, vp]
+    L.model_noise.argtypes = [C.c_uint64, C.c_uint64, C.c_int64, C.c_int64, vp, vp]
+    L.model_pnorm_awgn.argtypes = [vp, vp, C.c_int64, C.c_int64, C.c_int, C.c_float, C.c_uint64, C.c_uint64, vp]
+    L.model_gen_bits.argtypes = [C.c_uint64, C.c_uint64, C.c_int64, C.c_int, vp, vp]
+    L.model_count_errors.argtypes = [vp, vp, C.c_int64, C.c_int, vp, vp, vp]
+    L.model_num_steps.argtypes = [vp, C.POINTER(C.c_int)]
+    L.model_step_info.argtypes = [vp, C.c_int, C.POINTER(C.c_int), i64p]
+    L.model_get_activation.argtypes = [vp, C.c_int, vp, vp]
+    L.model_last_error.restype = C.c_char_p
+    for name in SYMBOLS:
+        if name not in ("model_destroy", "model_last_error"):
+            getattr(L, name).restype = C.c_int
+    return L
+
+
+lib = _load()
+
+
+def _check(rc):
+    if rc != 0:
+        raise AeError(rc, lib.model_last_error().decode())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t, dtype=None):
+    if t is None:
+        return C.c_void_p(0)
+    assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensor required"
+    if dtype is not None:
+        assert t.dtype == dtype, (t.dtype, dtype)
+    return C.c_void_p(t.data_ptr())
+
+
+def model_last_error():
+    return lib.model_last_error().decode()
+
+
+def model_describe(layer_spec, batch, dtype=AE_F32, bn_mode=0):
+    """Host-only: (n_params, in_chw, out_chw, latent_n, workspace_bytes)."""
+    n = C.c_int64()
+    lat = C.c_int64()
+    ws = C.c_int64()
+    ic = (C.c_int64 * 3)()
+    oc = (C.c_int64 * 3)()
+    _check(lib.model_describe(layer_spec.encode(), batch, dtype, bn_mode, C.byref(n), ic, oc, C.byref(lat), C.byref(ws)))
+    return n.value, tuple(ic), tuple(oc), lat.value, ws.value
+
+
+class Model:
+    """Owns one ae_model handle (model_create / model_destroy)."""
+
+    def __init__(self, layer_spec, batch, dtype=AE_F32, bn_mode=0):
+        self._h = C.c_void_p()
+        _check(lib.model_create(layer_spec.encode(), batch, dtype, bn_mode, C.byref(self._h)))
+        self.batch, self.dtype, self.bn_mode, self.spec = batch, dtype, bn_mode, layer_spec
+        self.tdtype = TORCH_DTYPE[dtype]
+        n = C.c_int64()
+        _check(lib.model_param_count(self._h, C.byref(n)))
+        self.n_params = n.value
+        ic = (C.c_int64 * 3)()
+        oc = (C.c_int64 * 3)()
+        lat = C.c_int64()
+        _check(lib.model_io_shape(self._h, ic, oc, C.byref(lat)))
+        self.in_shape, self.out_shape, self.latent_n = tuple(ic), tuple(oc), lat.value
+
+    def close(self):
+        if getattr(self, "_h", None) and self._h.value:
+            lib.model_destroy(self._h)
+            self._h = C.c_void_p()
+
+    __del__ = close
+
+    def model_set_sample_offset(self, first_sample):
+        _check(lib.model_set_sample_offset(self._h, first_sample))
+
+    def model_forward(self, params, x, snr_db, seed, y):
+        assert params.numel() == self.n_params and x.numel() == self.batch * _prod(self.in_shape)
+        assert y.numel() == self.batch * _prod(self.out_shape)
+        _check(lib.model_forward(self._h, _ptr(params, torch.float32), _ptr(x, self.tdtype), snr_db, seed,
+                                 _ptr(y, self.tdtype), _stream()))
+
+    def model_backward(self, params, x, dy, grads):
+        assert params.numel() == self.n_params and grads.numel() == self.n_params
+        assert dy.numel() == self.batch * _prod(self.out_shape)
+        _check(lib.model_backward(self._h, _ptr(params, torch.float32), _ptr(x, self.tdtype), _ptr(dy, self.tdtype),
+                                  _ptr(grads, torch.float32), _stream()))
+
+    def model_num_steps(self):
+        n = C.c_int()
+        _check(lib.model_num_steps(self._h, C.byref(n)))
+        return n.value
+
+    def model_step_info(self, step):
+        tok = C.c_int()
+        chw = (C.c_int64 * 3)()
+        _check(lib.model_step_info(self._h, step, C.byref(tok), chw))
+        return tok.value, tuple(chw)
+
+    def model_get_activation(self, step, out_nchw):
+        _check(lib.model_get_activation(self._h, step, _ptr(out_nchw, torch.float32), _stream()))
+
+
+def _prod(s):
+    p = 1
+    for v in s:
+        p *= int(v)
+    return p
+
+
+def model_loss_mse(y, target, loss_dev, dy=None):
+    dtype = AE_BF16 if y.dtype == torch.bfloat16 else AE_F32
+    assert target.dtype == y.dtype and target.numel() == y.numel()
+    _check(lib.model_loss_mse(_ptr(y), _ptr(target), y.numel(), dtype, _ptr(loss_dev, torch.float32),
+                              _ptr(dy, y.dtype) if dy is not None else C.c_void_p(0), _stream()))
+
+
+def model_noise(seed, first_sample, batch, n, out):
+    assert out.numel() == batch * n
+    _check(lib.model_noise(seed, first_sample, batch, n, _ptr(out, torch.float32), _stream()))
+
+
+def model_pnorm_awgn(z, y, batch, n, snr_db, seed, first_sample):
+    dtype = AE_BF16 if z.dtype == torch.bfloat16 else AE_F32
+    assert z.numel() == batch * n and y.numel() == batch * n and y.dtype == z.dtype
+    _check(lib.model_pnorm_awgn(_ptr(z), _ptr(y), batch, n, dtype, snr_db, seed, first_sample, _stream()))
+
+
+def model_gen_bits(seed, first_sample, batch, k, x_pm1):
+    assert x_pm1.numel() == batch * k
+    _check(lib.model_gen_bits(seed, first_sample, batch, k, _ptr(x_pm1, torch.float32), _stream()))
+
+
+def model_count_errors(y, x_pm1, batch, k, bit_err, blk_err):
+    assert y.numel() == batch * k and x_pm1.numel() == batch * k
+    assert bit_err.dtype == torch.int64 and blk_err.dtype == torch.int64
+    _check(lib.model_count_errors(_ptr(y, torch.float32), _ptr(x_pm1, torch.float32), batch, k, _ptr(bit_err),
+                                  _ptr(blk_err), _stream()))

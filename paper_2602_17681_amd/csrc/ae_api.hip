@@ -1,0 +1,345 @@
+// ae_api.hip — the exported C functions: model lifetime, and the host-side
+// executor that walks the plan and enqueues one kernel sequence per step.
+#include <math.h>
+#include <string.h>
+
+#include <new>
+
+#include "ae_internal.h"
+
+struct ae_model {
+  ae::Plan plan;
+  char* ws = nullptr;
+  void* grad_a = nullptr;
+  void* grad_b = nullptr;
+  void* draw = nullptr;
+  void* dfull = nullptr;
+  float* partial = nullptr;
+  uint64_t first_sample = 0;
+  bool have_forward = false;
+};
+
+using namespace ae;
+
+namespace {
+
+int nblocks_for(int64_t rows) { return (int)((rows + kReduceRows - 1) / kReduceRows); }
+
+// input tensor of step i: the previous step's saved output, or the caller's x
+const void* step_input(const ae_model* m, size_t i, const void* x) { return i == 0 ? x : m->plan.steps[i - 1].out; }
+
+int forward_conv(ae_model* m, Step& st, const float* params, const void* in, hipStream_t s) {
+  const Plan& P = m->plan;
+  const int64_t rows = (int64_t)P.batch * st.hc * st.wc;
+  const void* w;
+  if (st.k == 1 && P.dtype == AE_F32) {
+    w = params + st.w_off;  // [C_out][C_in] is already the packed order
+  } else {
+    AE_TRY(launch_pack_weights(params + st.w_off, st.wpack, st.cout, st.cin, st.k, P.dtype, false, s));
+    w = st.wpack;
+  }
+  const bool second_pass = st.has_bn || st.pool;
+  ConvArgs a;
+  a.x = in; a.w = w; a.bias = params + st.b_off;
+  a.y = second_pass ? st.raw : st.out;
+  a.n = P.batch; a.hc = st.hc; a.wc = st.wc; a.cin = st.cin; a.cout = st.cout; a.k = st.k; a.up = st.up;
+  a.act = second_pass ? ACT_NONE : st.act;
+  a.dtype = P.dtype;
+  a.partial = nullptr;
+  a.y_aux = second_pass ? nullptr : st.aux;
+  int nblk = 0;
+  if (st.mfma) {
+    if (st.has_bn && P.bn_mode == 0) { a.partial = m->partial; nblk = (int)((rows + conv_partial_rows(a, true) - 1) / conv_partial_rows(a, true)); }
+    AE_TRY(launch_conv_mfma(a, s));
+  } else {
+    AE_TRY(launch_conv_direct(a, s));
+  }
+  if (st.has_bn) {
+    const float* gb = params + st.bn_off;
+    if (P.bn_mode == 0) {
+      if (!a.partial) {
+        AE_TRY(launch_col_stats(st.raw, rows, st.cout, P.dtype, m->partial, s));
+        nblk = nblocks_for(rows);
+      }
+      AE_TRY(launch_bn_finalize(m->partial, nblk, rows, st.cout, gb, nullptr, st.bn_vec, s));
+    } else {
+      AE_TRY(launch_bn_finalize(nullptr, 0, rows, st.cout, gb, gb + 2 * st.cout, st.bn_vec, s));
+    }
+  }
+  if (second_pass)
+    AE_TRY(launch_post_forward(st.raw, st.has_bn ? st.bn_vec : nullptr, st.out, P.batch, st.hc, st.wc, st.cout, st.act,
+                               st.pool, P.dtype, s));
+  return AE_OK;
+}
+
+int backward_conv(ae_model* m, Step& st, const float* params, const void* in, const void* g, void* gnext, float* grads,
+                  hipStream_t s) {
+  const Plan& P = m->plan;
+  const int64_t rows = (int64_t)P.batch * st.hc * st.wc;
+  const void* dr = g;  // gradient w.r.t. the conv output (bias included)
+  if (st.has_bn || st.pool) {
+    if (st.has_bn) {
+      const int64_t prow = (int64_t)P.batch * st.hout * st.wout;
+      AE_TRY(launch_post_bwd_reduce(st.raw, g, st.bn_vec, P.batch, st.hc, st.wc, st.cout, st.act, st.pool, P.dtype,
+                                    m->partial, s));
+      AE_TRY(launch_bn_bwd_finalize(m->partial, nblocks_for(prow), rows, st.cout, params + st.bn_off, st.bn_vec,
+                                    grads + st.bn_off, P.bn_mode == 0, s));
+    }
+    AE_TRY(launch_post_bwd_apply(st.raw, g, st.has_bn ? st.bn_vec : nullptr, m->draw, P.batch, st.hc, st.wc, st.cout,
+                                 st.act, st.pool, st.has_bn, P.dtype, s));
+    dr = m->draw;
+  } else if (st.act != ACT_NONE) {
+    AE_TRY(launch_act_bwd(st.out, st.aux, g, m->draw, rows * st.cout, st.act, P.dtype, s));
+    dr = m->draw;
+  }
+  // bias gradient: column sums of the conv-output gradient
+  AE_TRY(launch_col_stats(dr, rows, st.cout, P.dtype, m->partial, s));
+  AE_TRY(launch_colsum_finalize(m->partial, nblocks_for(rows), st.cout, grads + st.b_off, s));
+  // weight gradient
+  const int64_t wel = (int64_t)st.cout * st.cin * st.k * st.k;
+  AE_TRY(launch_fill_zero(grads + st.w_off, wel * 4, s));
+  WgradArgs wa;
+  wa.x = in; wa.dy = dr; wa.dw_canonical = grads + st.w_off;
+  wa.n = P.batch; wa.hc = st.hc; wa.wc = st.wc; wa.cin = st.cin; wa.cout = st.cout; wa.k = st.k; wa.up = st.up;
+  wa.dtype = P.dtype;
+  AE_TRY(launch_wgrad_direct(wa, s));
+  // input gradient: convolution of dr with the flipped, transposed weights at conv resolution
+  if (st.needs_dx) {
+    AE_TRY(launch_pack_weights(params + st.w_off, st.wpack_d, st.cout, st.cin, st.k, P.dtype, true, s));
+    ConvArgs a;
+    a.x = dr; a.w = st.wpack_d; a.bias = nullptr;
+    a.y = st.up ? m->dfull : gnext;
+    a.n = P.batch; a.hc = st.hc; a.wc = st.wc; a.cin = st.cout; a.cout = st.cin; a.k = st.k; a.up = 0;
+    a.act = ACT_NONE; a.dtype = P.dtype; a.partial = nullptr; a.y_aux = nullptr;
+    if (conv_mfma_supported(a)) AE_TRY(launch_conv_mfma(a, s));
+    else AE_TRY(launch_conv_direct(a, s));
+    if (st.up) AE_TRY(launch_upsum(m->dfull, gnext, P.batch, st.hin, st.win, st.cin, P.dtype, s));
+  }
+  return AE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* model_last_error(void) { return ae::last_error(); }
+
+int model_describe(const char* layer_spec, int batch, int dtype, int bn_mode, int64_t* n_params, int64_t in_chw[3],
+                   int64_t out_chw[3], int64_t* latent_n, int64_t* workspace_bytes) {
+  Plan P;
+  AE_TRY(build_plan(layer_spec, batch, dtype, bn_mode, &P));
+  if (n_params) *n_params = P.n_params;
+  if (in_chw) { in_chw[0] = P.c0; in_chw[1] = P.h0; in_chw[2] = P.w0; }
+  if (out_chw) { out_chw[0] = P.cl; out_chw[1] = P.hl; out_chw[2] = P.wl; }
+  if (latent_n) *latent_n = P.latent_n;
+  if (workspace_bytes) *workspace_bytes = P.ws_bytes;
+  return AE_OK;
+}
+
+int model_create(const char* layer_spec, int batch, int dtype, int bn_mode, ae_model** out) {
+  if (!out) return fail(AE_EINVAL, "model_create: out is null");
+  *out = nullptr;
+  ae_model* m = new (std::nothrow) ae_model();
+  if (!m) return fail(AE_ENOMEM, "model_create: host allocation failed");
+  int rc = build_plan(layer_spec, batch, dtype, bn_mode, &m->plan);
+  if (rc != AE_OK) { delete m; return rc; }
+  hipError_t e = hipMalloc((void**)&m->ws, (size_t)m->plan.ws_bytes);
+  if (e != hipSuccess) {
+    delete m;
+    return fail(e == hipErrorOutOfMemory ? AE_ENOMEM : AE_EHIP, "model_create: hipMalloc(%lld bytes): %s",
+                (long long)m->plan.ws_bytes, hipGetErrorString(e));
+  }
+  Plan& P = m->plan;
+  for (Step& st : P.steps) {
+    st.out = st.off_out >= 0 ? m->ws + st.off_out : nullptr;
+    st.raw = st.off_raw >= 0 ? m->ws + st.off_raw : nullptr;
+    st.wpack = st.off_wpack >= 0 ? m->ws + st.off_wpack : nullptr;
+    st.wpack_d = st.off_wpack_d >= 0 ? m->ws + st.off_wpack_d : nullptr;
+    st.bn_vec = st.off_bn >= 0 ? (float*)(m->ws + st.off_bn) : nullptr;
+    st.aux = st.off_aux >= 0 ? (float*)(m->ws + st.off_aux) : nullptr;
+    if (st.kind == ST_CONV) {
+      ConvArgs a;
+      memset(&a, 0, sizeof(a));
+      a.n = P.batch; a.hc = st.hc; a.wc = st.wc; a.cin = st.cin; a.cout = st.cout; a.k = st.k; a.up = st.up;
+      a.dtype = P.dtype;
+      st.mfma = conv_mfma_supported(a);
+    }
+  }
+  m->grad_a = m->ws + P.off_grad_a;
+  m->grad_b = m->ws + P.off_grad_b;
+  m->draw = m->ws + P.off_draw;
+  m->dfull = m->ws + P.off_dfull;
+  m->partial = (float*)(m->ws + P.off_partial);
+  *out = m;
+  return AE_OK;
+}
+
+void model_destroy(ae_model* m) {
+  if (!m) return;
+  if (m->ws) (void)hipFree(m->ws);
+  delete m;
+}
+
+int model_param_count(const ae_model* m, int64_t* n_params) {
+  if (!m || !n_params) return fail(AE_EINVAL, "model_param_count: null argument");
+  *n_params = m->plan.n_params;
+  return AE_OK;
+}
+
+int model_io_shape(const ae_model* m, int64_t in_chw[3], int64_t out_chw[3], int64_t* latent_n) {
+  if (!m) return fail(AE_EINVAL, "model_io_shape: null model");
+  const Plan& P = m->plan;
+  if (in_chw) { in_chw[0] = P.c0; in_chw[1] = P.h0; in_chw[2] = P.w0; }
+  if (out_chw) { out_chw[0] = P.cl; out_chw[1] = P.hl; out_chw[2] = P.wl; }
+  if (latent_n) *latent_n = P.latent_n;
+  return AE_OK;
+}
+
+int model_set_sample_offset(ae_model* m, uint64_t first_sample) {
+  if (!m) return fail(AE_EINVAL, "model_set_sample_offset: null model");
+  m->first_sample = first_sample;
+  return AE_OK;
+}
+
+int model_forward(ae_model* m, const void* params, const void* x, float snr_db, uint64_t seed, void* y, void* stream) {
+  if (!m || !x || !y) return fail(AE_EINVAL, "model_forward: null argument");
+  Plan& P = m->plan;
+  if (!params && P.n_params > 0) return fail(AE_EINVAL, "model_forward: params is null");
+  if (!(snr_db == snr_db) || isinf(snr_db)) return fail(AE_EINVAL, "model_forward: snr_db is not finite");
+  hipStream_t s = (hipStream_t)stream;
+  const float* prm = (const float*)params;
+  const float sigma = (float)pow(10.0, -(double)snr_db / 20.0);
+  m->have_forward = false;
+  const size_t ns = P.steps.size();
+  for (size_t i = 0; i < ns; ++i) {
+    Step& st = P.steps[i];
+    const void* in = step_input(m, i, x);
+    switch (st.kind) {
+      case ST_TRANSPOSE: {
+        // the last step of a plan that ends in a transpose writes the caller's y directly
+        void* dst = (i + 1 == ns) ? y : st.out;
+        AE_TRY(launch_transpose(in, dst, P.batch, st.t_rows, st.t_cols, P.dtype, s));
+        break;
+      }
+      case ST_CONV:
+        AE_TRY(forward_conv(m, st, prm, in, s));
+        break;
+      case ST_CHANNEL:
+        AE_TRY(launch_pnorm_awgn(in, st.out, P.batch, st.cin, st.hin * st.win, P.dtype, st.do_pnorm, st.do_awgn, sigma,
+                                 seed, m->first_sample, s));
+        break;
+    }
+  }
+  if (P.steps[ns - 1].kind != ST_TRANSPOSE) {
+    const Step& st = P.steps[ns - 1];
+    size_t bytes = (size_t)P.batch * st.cout * st.hout * st.wout * dtype_size(P.dtype);
+    AE_HIP(hipMemcpyAsync(y, st.out, bytes, hipMemcpyDeviceToDevice, s));
+  }
+  m->have_forward = true;
+  return AE_OK;
+}
+
+int model_backward(ae_model* m, const void* params, const void* x, const void* dy, void* grads, void* stream) {
+  if (!m || !x || !dy) return fail(AE_EINVAL, "model_backward: null argument");
+  Plan& P = m->plan;
+  if ((!params || !grads) && P.n_params > 0) return fail(AE_EINVAL, "model_backward: params or grads is null");
+  if (!m->have_forward) return fail(AE_ESTATE, "model_backward: no forward pass on this handle to differentiate");
+  hipStream_t s = (hipStream_t)stream;
+  const float* prm = (const float*)params;
+  float* gr = (float*)grads;
+  const void* g = dy;
+  const size_t ns = P.steps.size();
+  // gradients flow only down to the first parametrised step
+  size_t first_param = ns;
+  for (size_t i = 0; i < ns; ++i)
+    if (P.steps[i].kind == ST_CONV) { first_param = i; break; }
+  for (size_t ii = ns; ii-- > first_param;) {
+    Step& st = P.steps[ii];
+    void* gnext = (g == m->grad_a) ? m->grad_b : m->grad_a;
+    const void* in = step_input(m, ii, x);
+    switch (st.kind) {
+      case ST_TRANSPOSE:
+        AE_TRY(launch_transpose(g, gnext, P.batch, st.t_cols, st.t_rows, P.dtype, s));
+        g = gnext;
+        break;
+      case ST_CHANNEL:
+        if (st.do_pnorm) {
+          AE_TRY(launch_pnorm_bwd(in, g, gnext, P.batch, (int64_t)st.cin * st.hin * st.win, P.dtype, s));
+          g = gnext;
+        }
+        break;
+      case ST_CONV:
+        AE_TRY(backward_conv(m, st, prm, in, g, gnext, gr, s));
+        if (st.needs_dx) g = gnext;
+        break;
+    }
+  }
+  return AE_OK;
+}
+
+int model_loss_mse(const void* y, const void* target, int64_t n_elem, int dtype, float* loss_dev, void* dy,
+                   void* stream) {
+  if (!y || !target || !loss_dev) return fail(AE_EINVAL, "model_loss_mse: null argument");
+  if (n_elem <= 0) return fail(AE_EINVAL, "model_loss_mse: n_elem must be positive");
+  if (dtype != AE_F32 && dtype != AE_BF16) return fail(AE_EINVAL, "model_loss_mse: bad dtype");
+  return launch_mse(y, target, n_elem, dtype, loss_dev, dy, (hipStream_t)stream);
+}
+
+int model_noise(uint64_t seed, uint64_t first_sample, int64_t batch, int64_t n, float* out, void* stream) {
+  if (!out) return fail(AE_EINVAL, "model_noise: out is null");
+  if (batch < 0 || n < 0 || n > ((int64_t)1 << 33)) return fail(AE_EINVAL, "model_noise: bad size");
+  if (batch == 0 || n == 0) return AE_OK;
+  return launch_noise(seed, first_sample, batch, n, out, (hipStream_t)stream);
+}
+
+int model_pnorm_awgn(const void* z, void* y, int64_t batch, int64_t n, int dtype, float snr_db, uint64_t seed,
+                     uint64_t first_sample, void* stream) {
+  if (!z || !y) return fail(AE_EINVAL, "model_pnorm_awgn: null argument");
+  if (batch < 0 || n <= 0 || n > 0x7FFFFFFF) return fail(AE_EINVAL, "model_pnorm_awgn: bad size");
+  if (dtype != AE_F32 && dtype != AE_BF16) return fail(AE_EINVAL, "model_pnorm_awgn: bad dtype");
+  if (batch == 0) return AE_OK;
+  const float sigma = (float)pow(10.0, -(double)snr_db / 20.0);
+  return launch_pnorm_awgn(z, y, batch, (int)n, 1, dtype, 1, 1, sigma, seed, first_sample, (hipStream_t)stream);
+}
+
+int model_gen_bits(uint64_t seed, uint64_t first_sample, int64_t batch, int k, float* x_pm1, void* stream) {
+  if (!x_pm1) return fail(AE_EINVAL, "model_gen_bits: null argument");
+  if (batch < 0 || k <= 0) return fail(AE_EINVAL, "model_gen_bits: bad size");
+  if (batch == 0) return AE_OK;
+  return launch_gen_bits(seed, first_sample, batch, k, x_pm1, (hipStream_t)stream);
+}
+
+int model_count_errors(const float* y, const float* x_pm1, int64_t batch, int k, uint64_t* bit_err, uint64_t* blk_err,
+                       void* stream) {
+  if (!y || !x_pm1 || !bit_err || !blk_err) return fail(AE_EINVAL, "model_count_errors: null argument");
+  if (batch < 0 || k <= 0) return fail(AE_EINVAL, "model_count_errors: bad size");
+  if (batch == 0) return AE_OK;
+  return launch_count_errors(y, x_pm1, batch, k, bit_err, blk_err, (hipStream_t)stream);
+}
+
+int model_num_steps(const ae_model* m, int* n_steps) {
+  if (!m || !n_steps) return fail(AE_EINVAL, "model_num_steps: null argument");
+  *n_steps = (int)m->plan.steps.size();
+  return AE_OK;
+}
+
+int model_step_info(const ae_model* m, int step, int* last_token, int64_t chw[3]) {
+  if (!m || step < 0 || step >= (int)m->plan.steps.size()) return fail(AE_EINVAL, "model_step_info: bad step");
+  const Step& st = m->plan.steps[step];
+  if (last_token) *last_token = st.last_token;
+  if (chw) { chw[0] = st.cout; chw[1] = st.hout; chw[2] = st.wout; }
+  return AE_OK;
+}
+
+int model_get_activation(ae_model* m, int step, float* out_nchw, void* stream) {
+  if (!m || !out_nchw || step < 0 || step >= (int)m->plan.steps.size())
+    return fail(AE_EINVAL, "model_get_activation: bad argument");
+  if (!m->have_forward) return fail(AE_ESTATE, "model_get_activation: no forward pass yet");
+  const Plan& P = m->plan;
+  const Step& st = P.steps[step];
+  if (step + 1 == (int)P.steps.size() && st.kind == ST_TRANSPOSE)
+    return fail(AE_EINVAL, "model_get_activation: the final layout step writes y directly and keeps no copy");
+  return launch_to_f32_nchw(st.out, out_nchw, P.batch, st.cout, st.hout * st.wout, P.dtype, (hipStream_t)stream);
+}
+
+}  // extern "C"

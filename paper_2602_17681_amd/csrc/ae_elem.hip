@@ -1,0 +1,557 @@
+// ae_elem.hip — the bandwidth-bound kernels around the convolutions:
+// layout changes, weight repacking, per-channel reductions, the fused
+// batch-norm / activation / max-pool second pass and its backward, the 2x2
+// gradient sum of the upsample, and the MSE loss.  All tensors are
+// [rows][C] with channels innermost; each thread moves 16-byte vectors along C.
+#include "ae_device.h"
+#include "ae_internal.h"
+
+namespace ae {
+namespace {
+
+constexpr int NT = 256;
+
+inline int grid_for(int64_t items, int per_block = NT, int cap = 65535 * 8) {
+  int64_t g = (items + per_block - 1) / per_block;
+  if (g < 1) g = 1;
+  if (g > cap) g = cap;
+  return (int)g;
+}
+
+// ---------------------------------------------------------------------------
+// per-sample transpose [rows][cols] -> [cols][rows]
+// ---------------------------------------------------------------------------
+template <typename TI, typename TO>
+__global__ void k_transpose(const TI* __restrict__ in, TO* __restrict__ out, int rows, int cols) {
+  __shared__ float tile[32][33];
+  const int64_t base = (int64_t)blockIdx.z * rows * cols;
+  const int c0 = blockIdx.x * 32, r0 = blockIdx.y * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+  for (int i = ty; i < 32; i += 8) {
+    int r = r0 + i, c = c0 + tx;
+    if (r < rows && c < cols) tile[i][tx] = Store<TI>::ld(in + base + (int64_t)r * cols + c);
+  }
+  __syncthreads();
+  for (int i = ty; i < 32; i += 8) {
+    int c = c0 + i, r = r0 + tx;
+    if (r < rows && c < cols) Store<TO>::st(out + base + (int64_t)c * rows + r, tile[tx][i]);
+  }
+}
+
+template <typename TI, typename TO>
+int transpose_impl(const void* in, void* out, int64_t batch, int rows, int cols, hipStream_t s) {
+  const int64_t zmax = 65535;
+  for (int64_t b0 = 0; b0 < batch; b0 += zmax) {
+    int nb = (int)std::min<int64_t>(zmax, batch - b0);
+    dim3 grid((cols + 31) / 32, (rows + 31) / 32, nb);
+    hipLaunchKernelGGL((k_transpose<TI, TO>), grid, dim3(256), 0, s, (const TI*)in + b0 * rows * cols,
+                       (TO*)out + b0 * rows * cols, rows, cols);
+  }
+  return launch_status("transpose");
+}
+
+// ---------------------------------------------------------------------------
+// weights: canonical fp32 W[co][ci][r][s] -> packed [co][r][s][ci] (forward) or
+// [ci][k-1-r][k-1-s][co] (the convolution that produces the input gradient)
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ void k_pack_weights(const float* __restrict__ w, T* __restrict__ wp, int cout, int cin, int k, int dgrad) {
+  const int64_t total = (int64_t)cout * cin * k * k;
+  for (int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x; i < total; i += (int64_t)gridDim.x * NT) {
+    // i enumerates the PACKED layout so that the stores coalesce
+    int64_t src;
+    if (!dgrad) {
+      int ci = (int)(i % cin); int64_t t = i / cin;
+      int s = (int)(t % k); t /= k;
+      int r = (int)(t % k); int co = (int)(t / k);
+      src = (((int64_t)co * cin + ci) * k + r) * k + s;
+    } else {
+      int co = (int)(i % cout); int64_t t = i / cout;
+      int s = (int)(t % k); t /= k;
+      int r = (int)(t % k); int ci = (int)(t / k);
+      src = (((int64_t)co * cin + ci) * k + (k - 1 - r)) * k + (k - 1 - s);
+    }
+    Store<T>::st(wp + i, w[src]);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Block-level helper: every thread holds NQ x VEC partial sums for channel group
+// `cg` (channels cbase + cg*VEC ...) accumulated over the rows of its row lane
+// `rl`; combine over row lanes and write partial_blk[q][channel].
+// ---------------------------------------------------------------------------
+template <int VEC, int NQ>
+__device__ __forceinline__ void block_col_combine(const float (&acc)[NQ][VEC], int cg, int rl, int nrl, int tpr,
+                                                  int cbase, int C, float* partial_blk, float* smem, bool active) {
+  __syncthreads();
+  if (active) {
+#pragma unroll
+    for (int q = 0; q < NQ; ++q)
+#pragma unroll
+      for (int v = 0; v < VEC; ++v) smem[((rl * tpr + cg) * NQ + q) * VEC + v] = acc[q][v];
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < tpr * NQ * VEC; i += NT) {
+    int v = i % VEC, q = (i / VEC) % NQ, g = i / (VEC * NQ);
+    int c = cbase + g * VEC + v;
+    if (c < C) {
+      float t = 0.0f;
+      for (int r = 0; r < nrl; ++r) t += smem[((r * tpr + g) * NQ + q) * VEC + v];
+      partial_blk[(int64_t)q * C + c] = t;
+    }
+  }
+}
+
+// partial[b][0][c] = sum over the block's rows of x, partial[b][1][c] = sum of x^2
+template <typename T, int VEC>
+__global__ void k_col_stats(const T* __restrict__ x, int64_t rows, int C, float* __restrict__ partial) {
+  __shared__ float smem[NT * 2 * VEC];
+  const int groups = (C + VEC - 1) / VEC;
+  const int tpr = groups < NT ? groups : NT;
+  const int nrl = NT / tpr;
+  const int cg = threadIdx.x % tpr, rl = threadIdx.x / tpr;
+  const bool active = rl < nrl;
+  const int64_t r0 = (int64_t)blockIdx.x * kReduceRows;
+  const int64_t r1 = r0 + kReduceRows < rows ? r0 + kReduceRows : rows;
+  float* pb = partial + (int64_t)blockIdx.x * 2 * C;
+  for (int cbase = 0; cbase < C; cbase += tpr * VEC) {
+    float acc[2][VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) acc[0][v] = acc[1][v] = 0.0f;
+    const int c = cbase + cg * VEC;
+    if (active && c < C) {
+      for (int64_t r = r0 + rl; r < r1; r += nrl) {
+        float v[VEC];
+        if (VEC == 1) v[0] = Store<T>::ld(x + r * C + c);
+        else Store<T>::ldv(x + r * C + c, reinterpret_cast<float(&)[Store<T>::VEC]>(v));
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) { acc[0][j] += v[j]; acc[1][j] += v[j] * v[j]; }
+      }
+    }
+    block_col_combine<VEC, 2>(acc, cg, rl, nrl, tpr, cbase, C, pb, smem, active);
+  }
+}
+
+// one block per channel: reduce the partials in double and derive the batch-norm vectors
+//   bn_vec = [scale | shift | mean | invstd | c1 | c2], scale = gamma*invstd, shift = beta - mean*scale
+__global__ void k_bn_finalize(const float* __restrict__ partial, int nblocks, double inv_rows, int C,
+                              const float* __restrict__ gamma_beta, const float* __restrict__ stored_mean_var,
+                              float* __restrict__ bn_vec) {
+  __shared__ double sm[NT / 64 + 1];
+  const int c = blockIdx.x;
+  double mean, var;
+  if (stored_mean_var) {
+    mean = (double)stored_mean_var[c];
+    var = (double)stored_mean_var[C + c];
+  } else {
+    double s1 = 0.0, s2 = 0.0;
+    for (int b = threadIdx.x; b < nblocks; b += NT) {
+      s1 += (double)partial[((int64_t)b * 2) * C + c];
+      s2 += (double)partial[((int64_t)b * 2 + 1) * C + c];
+    }
+    s1 = block_sum<NT>(s1, sm);
+    s2 = block_sum<NT>(s2, sm);
+    mean = s1 * inv_rows;
+    var = s2 * inv_rows - mean * mean;
+    if (var < 0.0) var = 0.0;
+  }
+  if (threadIdx.x == 0) {
+    double invstd = 1.0 / sqrt(var + 1e-5);
+    double scale = (double)gamma_beta[c] * invstd;
+    bn_vec[c] = (float)scale;
+    bn_vec[C + c] = (float)((double)gamma_beta[C + c] - mean * scale);
+    bn_vec[2 * C + c] = (float)mean;
+    bn_vec[3 * C + c] = (float)invstd;
+    bn_vec[4 * C + c] = 0.0f;
+    bn_vec[5 * C + c] = 0.0f;
+  }
+}
+
+template <typename T, int VEC>
+__device__ __forceinline__ void load_vec(const T* p, float (&v)[VEC]) {
+  if (VEC == 1) v[0] = Store<T>::ld(p);
+  else Store<T>::ldv(p, reinterpret_cast<float(&)[Store<T>::VEC]>(v));
+}
+template <typename T, int VEC>
+__device__ __forceinline__ void store_vec(T* p, const float (&v)[VEC]) {
+  if (VEC == 1) Store<T>::st(p, v[0]);
+  else Store<T>::stv(p, reinterpret_cast<const float(&)[Store<T>::VEC]>(v));
+}
+template <int VEC>
+__device__ __forceinline__ void load_f32(const float* p, float (&v)[VEC]) {
+#pragma unroll
+  for (int j = 0; j < VEC; ++j) v[j] = p[j];
+}
+
+// out = pool?( act( scale*raw + shift ) ); bn_vec == null means scale 1, shift 0
+template <typename T, int VEC>
+__global__ void k_post_forward(const T* __restrict__ raw, const float* __restrict__ bn_vec, T* __restrict__ out,
+                               int64_t n, int H, int W, int C, int act, int pool) {
+  const int groups = C / VEC;
+  const int Ho = H >> pool, Wo = W >> pool;
+  const int64_t total = n * Ho * Wo * groups;
+  for (int64_t it = (int64_t)blockIdx.x * NT + threadIdx.x; it < total; it += (int64_t)gridDim.x * NT) {
+    const int c = (int)(it % groups) * VEC;
+    int64_t p = it / groups;
+    const int wo = (int)(p % Wo); p /= Wo;
+    const int ho = (int)(p % Ho);
+    const int64_t b = p / Ho;
+    float sc[VEC], sh[VEC];
+    if (bn_vec) { load_f32<VEC>(bn_vec + c, sc); load_f32<VEC>(bn_vec + C + c, sh); }
+    else {
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) { sc[j] = 1.0f; sh[j] = 0.0f; }
+    }
+    float res[VEC];
+    if (pool) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        float v[VEC];
+        load_vec<T, VEC>(raw + ((b * H + 2 * ho + (q >> 1)) * W + 2 * wo + (q & 1)) * C + c, v);
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) {
+          float a = apply_act(fmaf(sc[j], v[j], sh[j]), act);
+          res[j] = (q == 0 || a > res[j]) ? a : res[j];
+        }
+      }
+    } else {
+      float v[VEC];
+      load_vec<T, VEC>(raw + ((b * H + ho) * W + wo) * C + c, v);
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) res[j] = apply_act(fmaf(sc[j], v[j], sh[j]), act);
+    }
+    store_vec<T, VEC>(out + ((b * Ho + ho) * Wo + wo) * C + c, res);
+  }
+}
+
+__device__ __forceinline__ float act_grad(float pre, float a, int act) {
+  if (act == 1) return pre > 0.0f ? 1.0f : 0.0f;
+  if (act == 2) return a * (1.0f - a);
+  return 1.0f;
+}
+
+// Backward of the second pass, shared by the reduction and the apply kernels: for
+// one output pixel (a 2x2 window when pooling) and VEC channels, find the routed
+// gradient dy_j at each raw position j and xhat_j.
+template <typename T, int VEC>
+struct PostBwdWindow {
+  float dy[4][VEC];
+  float xh[4][VEC];
+  __device__ __forceinline__ void compute(const T* __restrict__ raw, const T* __restrict__ dout,
+                                          const float* __restrict__ bn_vec, int64_t b, int ho, int wo, int H, int W,
+                                          int C, int c, int act, int pool) {
+    const int Ho = H >> pool, Wo = W >> pool;
+    float sc[VEC], sh[VEC], mu[VEC], is[VEC];
+    if (bn_vec) {
+      load_f32<VEC>(bn_vec + c, sc); load_f32<VEC>(bn_vec + C + c, sh);
+      load_f32<VEC>(bn_vec + 2 * C + c, mu); load_f32<VEC>(bn_vec + 3 * C + c, is);
+    } else {
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) { sc[j] = 1.0f; sh[j] = 0.0f; mu[j] = 0.0f; is[j] = 1.0f; }
+    }
+    float g[VEC];
+    load_vec<T, VEC>(dout + ((b * Ho + ho) * Wo + wo) * C + c, g);
+    const int nq = pool ? 4 : 1;
+    float best[VEC], dbest[VEC];
+    int arg[VEC];
+    for (int q = 0; q < nq; ++q) {
+      float v[VEC];
+      const int hh = pool ? 2 * ho + (q >> 1) : ho, ww = pool ? 2 * wo + (q & 1) : wo;
+      load_vec<T, VEC>(raw + ((b * H + hh) * W + ww) * C + c, v);
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) {
+        float pre = fmaf(sc[j], v[j], sh[j]);
+        float a = apply_act(pre, act);
+        xh[q][j] = (v[j] - mu[j]) * is[j];
+        dy[q][j] = 0.0f;
+        if (q == 0 || a > best[j]) { best[j] = a; arg[j] = q; dbest[j] = act_grad(pre, a, act); }
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (q < nq && arg[j] == q) dy[q][j] = g[j] * dbest[j];
+    }
+  }
+};
+
+// partial[b][0][c] = sum dy, partial[b][1][c] = sum dy*xhat over the block's output pixels
+template <typename T, int VEC>
+__global__ void k_post_bwd_reduce(const T* __restrict__ raw, const T* __restrict__ dout,
+                                  const float* __restrict__ bn_vec, int64_t n, int H, int W, int C, int act, int pool,
+                                  float* __restrict__ partial) {
+  __shared__ float smem[NT * 2 * VEC];
+  const int Ho = H >> pool, Wo = W >> pool;
+  const int64_t rows = n * Ho * Wo;
+  const int groups = (C + VEC - 1) / VEC;
+  const int tpr = groups < NT ? groups : NT;
+  const int nrl = NT / tpr;
+  const int cg = threadIdx.x % tpr, rl = threadIdx.x / tpr;
+  const bool active = rl < nrl;
+  const int64_t r0 = (int64_t)blockIdx.x * kReduceRows;
+  const int64_t r1 = r0 + kReduceRows < rows ? r0 + kReduceRows : rows;
+  float* pb = partial + (int64_t)blockIdx.x * 2 * C;
+  for (int cbase = 0; cbase < C; cbase += tpr * VEC) {
+    float acc[2][VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) acc[0][v] = acc[1][v] = 0.0f;
+    const int c = cbase + cg * VEC;
+    if (active && c < C) {
+      for (int64_t r = r0 + rl; r < r1; r += nrl) {
+        const int wo = (int)(r % Wo);
+        const int ho = (int)((r / Wo) % Ho);
+        const int64_t b = r / ((int64_t)Wo * Ho);
+        PostBwdWindow<T, VEC> win;
+        win.compute(raw, dout, bn_vec, b, ho, wo, H, W, C, c, act, pool);
+        const int nq = pool ? 4 : 1;
+        for (int q = 0; q < nq; ++q)
+#pragma unroll
+          for (int j = 0; j < VEC; ++j) { acc[0][j] += win.dy[q][j]; acc[1][j] += win.dy[q][j] * win.xh[q][j]; }
+      }
+    }
+    block_col_combine<VEC, 2>(acc, cg, rl, nrl, tpr, cbase, C, pb, smem, active);
+  }
+}
+
+// one block per channel: dgamma = sum dy*xhat, dbeta = sum dy; c1 = dbeta/M, c2 = dgamma/M (batch statistics)
+__global__ void k_bn_bwd_finalize(const float* __restrict__ partial, int nblocks, double inv_rows, int C,
+                                  float* __restrict__ bn_vec, float* __restrict__ dgamma_dbeta, int batch_stats,
+                                  int stored_slots) {
+  __shared__ double sm[NT / 64 + 1];
+  const int c = blockIdx.x;
+  double s1 = 0.0, s2 = 0.0;
+  for (int b = threadIdx.x; b < nblocks; b += NT) {
+    s1 += (double)partial[((int64_t)b * 2) * C + c];
+    s2 += (double)partial[((int64_t)b * 2 + 1) * C + c];
+  }
+  s1 = block_sum<NT>(s1, sm);
+  s2 = block_sum<NT>(s2, sm);
+  if (threadIdx.x == 0) {
+    dgamma_dbeta[c] = (float)s2;
+    dgamma_dbeta[C + c] = (float)s1;
+    if (stored_slots) { dgamma_dbeta[2 * C + c] = 0.0f; dgamma_dbeta[3 * C + c] = 0.0f; }
+    bn_vec[4 * C + c] = batch_stats ? (float)(s1 * inv_rows) : 0.0f;
+    bn_vec[5 * C + c] = batch_stats ? (float)(s2 * inv_rows) : 0.0f;
+  }
+}
+
+// draw_j = scale*(dy_j - c1 - xhat_j*c2) with batch-norm, dy_j without
+template <typename T, int VEC>
+__global__ void k_post_bwd_apply(const T* __restrict__ raw, const T* __restrict__ dout,
+                                 const float* __restrict__ bn_vec, T* __restrict__ draw, int64_t n, int H, int W,
+                                 int C, int act, int pool, int has_bn) {
+  const int groups = C / VEC;
+  const int Ho = H >> pool, Wo = W >> pool;
+  const int64_t total = n * Ho * Wo * groups;
+  for (int64_t it = (int64_t)blockIdx.x * NT + threadIdx.x; it < total; it += (int64_t)gridDim.x * NT) {
+    const int c = (int)(it % groups) * VEC;
+    int64_t p = it / groups;
+    const int wo = (int)(p % Wo); p /= Wo;
+    const int ho = (int)(p % Ho);
+    const int64_t b = p / Ho;
+    PostBwdWindow<T, VEC> win;
+    win.compute(raw, dout, bn_vec, b, ho, wo, H, W, C, c, act, pool);
+    float sc[VEC], c1[VEC], c2[VEC];
+    if (has_bn) { load_f32<VEC>(bn_vec + c, sc); load_f32<VEC>(bn_vec + 4 * C + c, c1); load_f32<VEC>(bn_vec + 5 * C + c, c2); }
+    const int nq = pool ? 4 : 1;
+    for (int q = 0; q < nq; ++q) {
+      float o[VEC];
+#pragma unroll
+      for (int j = 0; j < VEC; ++j)
+        o[j] = has_bn ? sc[j] * (win.dy[q][j] - c1[j] - win.xh[q][j] * c2[j]) : win.dy[q][j];
+      const int hh = pool ? 2 * ho + (q >> 1) : ho, ww = pool ? 2 * wo + (q & 1) : wo;
+      store_vec<T, VEC>(draw + ((b * H + hh) * W + ww) * C + c, o);
+    }
+  }
+}
+
+// draw = dout * act'(out), from the saved activation output
+template <typename T>
+__global__ void k_act_bwd(const T* __restrict__ out, const float* __restrict__ out_f32, const T* __restrict__ dout,
+                          T* __restrict__ draw, int64_t n, int act) {
+  for (int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x; i < n; i += (int64_t)gridDim.x * NT) {
+    float a = out_f32 ? out_f32[i] : Store<T>::ld(out + i), g = Store<T>::ld(dout + i);
+    float d = act == 1 ? (a > 0.0f ? 1.0f : 0.0f) : (act == 2 ? a * (1.0f - a) : 1.0f);
+    Store<T>::st(draw + i, g * d);
+  }
+}
+
+__global__ void k_colsum_finalize(const float* __restrict__ partial, int nblocks, int C, float* __restrict__ out) {
+  __shared__ double sm[NT / 64 + 1];
+  const int c = blockIdx.x;
+  double s1 = 0.0;
+  for (int b = threadIdx.x; b < nblocks; b += NT) s1 += (double)partial[((int64_t)b * 2) * C + c];
+  s1 = block_sum<NT>(s1, sm);
+  if (threadIdx.x == 0) out[c] = (float)s1;
+}
+
+// dx[n,i,j,c] = sum of the four copies' gradients
+template <typename T, int VEC>
+__global__ void k_upsum(const T* __restrict__ dfull, T* __restrict__ dx, int64_t n, int H, int W, int C) {
+  const int groups = C / VEC;
+  const int64_t total = n * H * W * groups;
+  for (int64_t it = (int64_t)blockIdx.x * NT + threadIdx.x; it < total; it += (int64_t)gridDim.x * NT) {
+    const int c = (int)(it % groups) * VEC;
+    int64_t p = it / groups;
+    const int j = (int)(p % W); p /= W;
+    const int i = (int)(p % H);
+    const int64_t b = p / H;
+    float acc[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) acc[v] = 0.0f;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      float v[VEC];
+      load_vec<T, VEC>(dfull + ((b * 2 * H + 2 * i + (q >> 1)) * 2 * W + 2 * j + (q & 1)) * C + c, v);
+#pragma unroll
+      for (int t = 0; t < VEC; ++t) acc[t] += v[t];
+    }
+    store_vec<T, VEC>(dx + ((b * H + i) * W + j) * C + c, acc);
+  }
+}
+
+__global__ void k_fill_zero(uint32_t* p, int64_t n_words) {
+  for (int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x; i < n_words; i += (int64_t)gridDim.x * NT) p[i] = 0u;
+}
+
+// loss += sum((y-t)^2)/n over the block's slice; dy = 2 (y-t)/n
+template <typename T>
+__global__ void k_mse(const T* __restrict__ y, const T* __restrict__ t, int64_t n, float inv_n, float* __restrict__ loss,
+                      T* __restrict__ dy) {
+  __shared__ float sm[NT / 64 + 1];
+  float acc = 0.0f;
+  for (int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x; i < n; i += (int64_t)gridDim.x * NT) {
+    float d = Store<T>::ld(y + i) - Store<T>::ld(t + i);
+    acc = fmaf(d, d, acc);
+    if (dy) Store<T>::st(dy + i, 2.0f * d * inv_n);
+  }
+  acc = block_sum<NT>(acc, sm);
+  if (threadIdx.x == 0) atomicAdd(loss, acc * inv_n);
+}
+
+}  // namespace
+
+// ===========================================================================
+// launchers
+// ===========================================================================
+#define DISPATCH_T(dtype, ...)                                  \
+  do {                                                          \
+    if ((dtype) == AE_BF16) { typedef bf16_t T; __VA_ARGS__; }  \
+    else { typedef float T; __VA_ARGS__; }                      \
+  } while (0)
+
+#define DISPATCH_T_VEC(dtype, C, ...)                                                       \
+  do {                                                                                      \
+    if ((dtype) == AE_BF16) {                                                               \
+      typedef bf16_t T;                                                                     \
+      if ((C) % 8 == 0) { constexpr int VEC = 8; __VA_ARGS__; } else { constexpr int VEC = 1; __VA_ARGS__; } \
+    } else {                                                                                \
+      typedef float T;                                                                      \
+      if ((C) % 4 == 0) { constexpr int VEC = 4; __VA_ARGS__; } else { constexpr int VEC = 1; __VA_ARGS__; } \
+    }                                                                                       \
+  } while (0)
+
+int launch_transpose(const void* in, void* out, int64_t batch, int rows, int cols, int dtype, hipStream_t s) {
+  if (dtype == AE_BF16) return transpose_impl<bf16_t, bf16_t>(in, out, batch, rows, cols, s);
+  return transpose_impl<float, float>(in, out, batch, rows, cols, s);
+}
+
+int launch_to_f32_nchw(const void* in_nhwc, float* out_nchw, int64_t batch, int c, int hw, int dtype, hipStream_t s) {
+  // stored [hw][c] -> [c][hw]
+  if (dtype == AE_BF16) return transpose_impl<bf16_t, float>(in_nhwc, out_nchw, batch, hw, c, s);
+  return transpose_impl<float, float>(in_nhwc, out_nchw, batch, hw, c, s);
+}
+
+int launch_pack_weights(const float* w, void* wp, int cout, int cin, int k, int dtype, bool for_dgrad, hipStream_t s) {
+  int64_t total = (int64_t)cout * cin * k * k;
+  DISPATCH_T(dtype, hipLaunchKernelGGL((k_pack_weights<T>), dim3(grid_for(total, NT, 4096)), dim3(NT), 0, s, w, (T*)wp,
+                                       cout, cin, k, for_dgrad ? 1 : 0));
+  return launch_status("pack_weights");
+}
+
+int launch_col_stats(const void* x, int64_t rows, int c, int dtype, float* partial, hipStream_t s) {
+  int nblocks = (int)((rows + kReduceRows - 1) / kReduceRows);
+  DISPATCH_T_VEC(dtype, c, hipLaunchKernelGGL((k_col_stats<T, VEC>), dim3(nblocks), dim3(NT), 0, s, (const T*)x, rows,
+                                              c, partial));
+  return launch_status("col_stats");
+}
+
+int launch_bn_finalize(const float* partial, int nblocks, int64_t rows, int c, const float* gamma_beta,
+                       const float* stored_mean_var, float* bn_vec, hipStream_t s) {
+  hipLaunchKernelGGL(k_bn_finalize, dim3(c), dim3(NT), 0, s, partial, nblocks, 1.0 / (double)rows, c, gamma_beta,
+                     stored_mean_var, bn_vec);
+  return launch_status("bn_finalize");
+}
+
+int launch_post_forward(const void* raw, const float* bn_vec, void* out, int64_t n, int h, int w, int c, int act,
+                        int pool, int dtype, hipStream_t s) {
+  DISPATCH_T_VEC(dtype, c, {
+    int64_t items = n * (h >> pool) * (w >> pool) * (c / VEC);
+    hipLaunchKernelGGL((k_post_forward<T, VEC>), dim3(grid_for(items)), dim3(NT), 0, s, (const T*)raw, bn_vec, (T*)out,
+                       n, h, w, c, act, pool);
+  });
+  return launch_status("post_forward");
+}
+
+int launch_post_bwd_reduce(const void* raw, const void* dout, const float* bn_vec, int64_t n, int h, int w, int c,
+                           int act, int pool, int dtype, float* partial, hipStream_t s) {
+  int64_t rows = n * (h >> pool) * (w >> pool);
+  int nblocks = (int)((rows + kReduceRows - 1) / kReduceRows);
+  DISPATCH_T_VEC(dtype, c, hipLaunchKernelGGL((k_post_bwd_reduce<T, VEC>), dim3(nblocks), dim3(NT), 0, s,
+                                              (const T*)raw, (const T*)dout, bn_vec, n, h, w, c, act, pool, partial));
+  return launch_status("post_bwd_reduce");
+}
+
+int launch_bn_bwd_finalize(const float* partial, int nblocks, int64_t rows, int c, const float* gamma, float* bn_vec,
+                           float* dgamma_dbeta, int batch_stats, hipStream_t s) {
+  (void)gamma;
+  hipLaunchKernelGGL(k_bn_bwd_finalize, dim3(c), dim3(NT), 0, s, partial, nblocks, 1.0 / (double)rows, c, bn_vec,
+                     dgamma_dbeta, batch_stats, batch_stats ? 0 : 1);
+  return launch_status("bn_bwd_finalize");
+}
+
+int launch_post_bwd_apply(const void* raw, const void* dout, const float* bn_vec, void* draw, int64_t n, int h, int w,
+                          int c, int act, int pool, int has_bn, int dtype, hipStream_t s) {
+  DISPATCH_T_VEC(dtype, c, {
+    int64_t items = n * (h >> pool) * (w >> pool) * (c / VEC);
+    hipLaunchKernelGGL((k_post_bwd_apply<T, VEC>), dim3(grid_for(items)), dim3(NT), 0, s, (const T*)raw,
+                       (const T*)dout, bn_vec, (T*)draw, n, h, w, c, act, pool, has_bn);
+  });
+  return launch_status("post_bwd_apply");
+}
+
+int launch_act_bwd(const void* out, const float* out_f32, const void* dout, void* draw, int64_t n_elem, int act,
+                   int dtype, hipStream_t s) {
+  DISPATCH_T(dtype, hipLaunchKernelGGL((k_act_bwd<T>), dim3(grid_for(n_elem, NT, 16384)), dim3(NT), 0, s,
+                                       (const T*)out, out_f32, (const T*)dout, (T*)draw, n_elem, act));
+  return launch_status("act_bwd");
+}
+
+int launch_colsum_finalize(const float* partial, int nblocks, int c, float* out, hipStream_t s) {
+  hipLaunchKernelGGL(k_colsum_finalize, dim3(c), dim3(NT), 0, s, partial, nblocks, c, out);
+  return launch_status("colsum_finalize");
+}
+
+int launch_upsum(const void* dfull, void* dx, int64_t n, int h, int w, int c, int dtype, hipStream_t s) {
+  DISPATCH_T_VEC(dtype, c, {
+    int64_t items = n * h * w * (c / VEC);
+    hipLaunchKernelGGL((k_upsum<T, VEC>), dim3(grid_for(items)), dim3(NT), 0, s, (const T*)dfull, (T*)dx, n, h, w, c);
+  });
+  return launch_status("upsum");
+}
+
+int launch_fill_zero(void* p, int64_t bytes, hipStream_t s) {
+  int64_t words = (bytes + 3) / 4;  // buffers are 4-byte multiples
+  hipLaunchKernelGGL(k_fill_zero, dim3(grid_for(words, NT, 8192)), dim3(NT), 0, s, (uint32_t*)p, words);
+  return launch_status("fill_zero");
+}
+
+int launch_mse(const void* y, const void* t, int64_t n, int dtype, float* loss, void* dy, hipStream_t s) {
+  AE_TRY(launch_fill_zero(loss, 4, s));
+  DISPATCH_T(dtype, hipLaunchKernelGGL((k_mse<T>), dim3(grid_for(n, NT * 8, 2048)), dim3(NT), 0, s, (const T*)y,
+                                       (const T*)t, n, (float)(1.0 / (double)n), loss, (T*)dy));
+  return launch_status("mse");
+}
+
+}  // namespace ae

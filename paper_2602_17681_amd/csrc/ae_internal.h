@@ -1,0 +1,147 @@
+// ae_internal.h — declarations shared by the translation units of libaemodel.
+// Host-side plan structures, error plumbing and the launcher prototypes of every
+// kernel family.  Nothing here is visible across the C boundary.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "aemodel.h"
+
+namespace ae {
+
+// ---- error plumbing --------------------------------------------------------
+int fail(int code, const char* fmt, ...);  // records the thread-local message, returns code
+const char* last_error();
+#define AE_HIP(expr)                                                                      \
+  do {                                                                                    \
+    hipError_t e_ = (expr);                                                               \
+    if (e_ != hipSuccess) return ae::fail(AE_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+#define AE_TRY(expr)          \
+  do {                        \
+    int rc_ = (expr);         \
+    if (rc_ != AE_OK) return rc_; \
+  } while (0)
+
+inline int launch_status(const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(AE_EHIP, "launch %s: %s", what, hipGetErrorString(e));
+  return AE_OK;
+}
+
+inline size_t dtype_size(int dtype) { return dtype == AE_BF16 ? 2 : 4; }
+
+// ---- plan ------------------------------------------------------------------
+enum StepKind { ST_TRANSPOSE = 0, ST_CONV = 1, ST_CHANNEL = 2 };
+enum Act { ACT_NONE = 0, ACT_RELU = 1, ACT_SIGMOID = 2 };
+
+// One fused step of the pipeline.  Activations are stored [batch][H][W][C]
+// (channels innermost) between steps; `flat` tensors (H = W = 1) coincide with
+// the (c,h,w)-ordered vector the spec talks about.
+struct Step {
+  StepKind kind = ST_CONV;
+  int last_token = -1;              // index of the last spec token folded into this step
+  int cin = 0, hin = 0, win = 0;    // stored input tensor
+  int cout = 0, hout = 0, wout = 0; // stored output tensor
+  // ST_TRANSPOSE: per-sample [rows][cols] -> [cols][rows]
+  int t_rows = 0, t_cols = 0;
+  // ST_CONV (conv1 / conv3 / fc, optionally reading its input through a x2 nearest upsample)
+  int k = 1, up = 0, has_bn = 0, act = ACT_NONE, pool = 0;
+  int hc = 0, wc = 0;               // resolution the convolution runs at
+  int64_t w_off = -1, b_off = -1, bn_off = -1;  // offsets into the parameter blob
+  bool needs_dx = true;             // false for the first parametrised step
+  // ST_CHANNEL (pnorm and/or awgn)
+  int do_pnorm = 0, do_awgn = 0;
+  // byte offsets into the model workspace (-1: not allocated), resolved to the pointers below at creation
+  int64_t off_out = -1, off_raw = -1, off_wpack = -1, off_wpack_d = -1, off_bn = -1, off_aux = -1;
+  // device workspace (owned by the model)
+  void* out = nullptr;              // saved output (model dtype)
+  void* raw = nullptr;              // conv output before bn/act/pool when those run as a second pass
+  void* wpack = nullptr;            // weights repacked [C_out][k][k][C_in] in model dtype (null: use params directly)
+  void* wpack_d = nullptr;          // weights repacked for the input-gradient conv [C_in][k][k][C_out], taps flipped
+  float* bn_vec = nullptr;          // 6*C floats: scale, shift, mean, invstd, c1, c2
+  float* aux = nullptr;             // binary32 copy of a sigmoid output produced in the conv epilogue (bf16 models):
+                                    // y*(1-y) from a bf16-rounded y loses all accuracy where the sigmoid saturates
+  bool mfma = false;                // forward uses the MFMA implicit-GEMM kernel
+};
+
+struct Plan {
+  int batch = 0, dtype = AE_F32, bn_mode = 0;
+  int c0 = 0, h0 = 0, w0 = 0;       // boundary input (NCHW)
+  int cl = 0, hl = 0, wl = 0;       // boundary output
+  int64_t n_params = 0;
+  int64_t latent_n = 0;
+  std::vector<Step> steps;
+  // workspace sizing (bytes)
+  int64_t ws_bytes = 0;
+  int64_t off_grad_a = 0, off_grad_b = 0, off_draw = 0, off_dfull = 0, off_partial = 0;
+  int64_t max_act_elems = 0;        // largest step output
+  int64_t max_raw_elems = 0;        // largest conv-resolution tensor (raw / dRaw)
+  int64_t max_full_elems = 0;       // largest conv-resolution input gradient of an upsampled conv
+  int64_t max_partial_floats = 0;   // column-reduction partial buffer
+};
+
+int build_plan(const char* spec, int batch, int dtype, int bn_mode, Plan* plan);
+
+// Rows of a column reduction handled by one block (partial-sum granularity).
+constexpr int kReduceRows = 256;
+
+// ---- launchers (all asynchronous on `s`) -----------------------------------
+// layout / dtype
+int launch_transpose(const void* in, void* out, int64_t batch, int rows, int cols, int dtype, hipStream_t s);
+int launch_to_f32_nchw(const void* in_nhwc, float* out_nchw, int64_t batch, int c, int hw, int dtype, hipStream_t s);
+
+// weights
+int launch_pack_weights(const float* w, void* wp, int cout, int cin, int k, int dtype, bool for_dgrad, hipStream_t s);
+
+// convolution family (direct kernels; see ae_conv.hip for the MFMA ones)
+struct ConvArgs {
+  const void* x; const void* w; const float* bias; void* y;
+  int n, hc, wc, cin, cout, k, up, act, dtype;
+  float* partial;  // nullable: per-row-block column sums / sums of squares of the fp32 result
+  float* y_aux;    // nullable: binary32 copy of y (after the activation)
+};
+int launch_conv_direct(const ConvArgs& a, hipStream_t s);
+bool conv_mfma_supported(const ConvArgs& a);
+int launch_conv_mfma(const ConvArgs& a, hipStream_t s);
+int conv_partial_rows(const ConvArgs& a, bool mfma);  // rows per partial-sum block of the kernel that will run
+
+struct WgradArgs {
+  const void* x; const void* dy; float* dw_canonical;  // dw is accumulated with atomics: must be zeroed first
+  int n, hc, wc, cin, cout, k, up, dtype;
+};
+int launch_wgrad_direct(const WgradArgs& a, hipStream_t s);
+
+// per-channel reductions and the second pass after a conv
+int launch_col_stats(const void* x, int64_t rows, int c, int dtype, float* partial, hipStream_t s);
+int launch_bn_finalize(const float* partial, int nblocks, int64_t rows, int c, const float* gamma_beta,
+                       const float* stored_mean_var, float* bn_vec, hipStream_t s);
+int launch_post_forward(const void* raw, const float* bn_vec, void* out, int64_t n, int h, int w, int c, int act,
+                        int pool, int dtype, hipStream_t s);
+int launch_post_bwd_reduce(const void* raw, const void* dout, const float* bn_vec, int64_t n, int h, int w, int c,
+                           int act, int pool, int dtype, float* partial, hipStream_t s);
+int launch_bn_bwd_finalize(const float* partial, int nblocks, int64_t rows, int c, const float* gamma, float* bn_vec,
+                           float* dgamma_dbeta, int batch_stats, hipStream_t s);
+int launch_post_bwd_apply(const void* raw, const void* dout, const float* bn_vec, void* draw, int64_t n, int h, int w,
+                          int c, int act, int pool, int has_bn, int dtype, hipStream_t s);
+int launch_act_bwd(const void* out, const float* out_f32, const void* dout, void* draw, int64_t n_elem, int act,
+                   int dtype, hipStream_t s);
+int launch_colsum_finalize(const float* partial, int nblocks, int c, float* out, hipStream_t s);
+int launch_upsum(const void* dfull, void* dx, int64_t n, int h, int w, int c, int dtype, hipStream_t s);
+int launch_fill_zero(void* p, int64_t bytes, hipStream_t s);
+
+// channel (power normalisation + noise), Monte-Carlo bookkeeping, loss
+int launch_pnorm_awgn(const void* z, void* y, int64_t batch, int c, int hw, int dtype, int do_pnorm, int do_awgn,
+                      float sigma, uint64_t seed, uint64_t first_sample, hipStream_t s);
+int launch_pnorm_bwd(const void* z, const void* g, void* dz, int64_t batch, int64_t n, int dtype, hipStream_t s);
+int launch_noise(uint64_t seed, uint64_t first_sample, int64_t batch, int64_t n, float* out, hipStream_t s);
+int launch_gen_bits(uint64_t seed, uint64_t first_sample, int64_t batch, int k, float* x, hipStream_t s);
+int launch_count_errors(const float* y, const float* x, int64_t batch, int k, uint64_t* bit_err, uint64_t* blk_err,
+                        hipStream_t s);
+int launch_mse(const void* y, const void* t, int64_t n, int dtype, float* loss, void* dy, hipStream_t s);
+
+}  // namespace ae

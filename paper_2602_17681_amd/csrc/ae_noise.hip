@@ -1,0 +1,305 @@
+// ae_noise.hip — the channel: per-sample power normalisation fused with additive
+// white Gaussian noise drawn from Philox4x32-10, its backward, and the
+// Monte-Carlo bookkeeping kernels (message bits, error counts).
+//
+// Counter layout: key = (seed_lo, seed_hi); counter = (sample_lo, sample_hi,
+// quad, stream) with `sample` the global sample index, `quad` = element index / 4
+// in (c,h,w) order, stream 0 = channel noise, 1 = message bits.  The u32 -> normal
+// map is a fixed sequence of correctly rounded binary32 operations (explicit
+// round-to-nearest intrinsics, never contracted), so the noise tensor is
+// reproducible bit for bit.
+#include "ae_device.h"
+#include "ae_internal.h"
+
+namespace ae {
+namespace {
+
+constexpr int NT = 256;
+
+struct U4 { uint32_t x, y, z, w; };
+
+__device__ __forceinline__ U4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                            uint32_t k1) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+    const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    c1 = (uint32_t)p1;
+    c3 = (uint32_t)p0;
+    c0 = n0;
+    c2 = n2;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  return U4{c0, c1, c2, c3};
+}
+
+// ln(u) for u in [2^-33, 1]: u = m 2^e, m in [sqrt(1/2), sqrt(2)); ln(1+f) = f + f^2 Q(f)
+__device__ __forceinline__ float ln_unit(float u) {
+  const uint32_t bits = __float_as_uint(u);
+  int e = (int)(bits >> 23) - 127;
+  const uint32_t mant = bits & 0x007FFFFFu;
+  float m = __uint_as_float(mant | 0x3F800000u);
+  if (mant > 0x003504F3u) { m = __fmul_rn(m, 0.5f); e += 1; }
+  const float f = __fadd_rn(m, -1.0f);
+  float q = -0x1.383e66p-4f;
+  q = __fmaf_rn(q, f, 0x1.084e9p-3f);
+  q = __fmaf_rn(q, f, -0x1.0f3778p-3f);
+  q = __fmaf_rn(q, f, 0x1.227084p-3f);
+  q = __fmaf_rn(q, f, -0x1.542744p-3f);
+  q = __fmaf_rn(q, f, 0x1.99a402p-3f);
+  q = __fmaf_rn(q, f, -0x1.000428p-2f);
+  q = __fmaf_rn(q, f, 0x1.55555p-2f);
+  q = __fmaf_rn(q, f, -0x1.fffff8p-2f);
+  const float f2 = __fmul_rn(f, f);
+  const float l1 = __fmaf_rn(f2, q, f);
+  return __fmaf_rn((float)e, 0x1.62e43p-1f, l1);
+}
+
+// Box-Muller on two words; see the header's description of model_noise.
+__device__ __forceinline__ void gauss_pair(uint32_t w0, uint32_t w1, float& g0, float& g1) {
+  const float u = __fmaf_rn(__uint2float_rn(w0), 0x1p-32f, 0x1p-33f);
+  const float rho = sqrtf(__fmul_rn(-2.0f, ln_unit(u)));  // sqrtf is correctly rounded (-fhip-fp32-correctly-rounded-divide-sqrt); __fsqrt_rn is not
+  const uint32_t quadrant = w1 >> 30;
+  const float t = __fmul_rn(__uint2float_rn((w1 >> 6) & 0x00FFFFFFu), 0x1p-24f);
+  const bool swap = t > 0.5f;
+  const float r = swap ? __fadd_rn(1.0f, -t) : t;
+  const float z = __fmul_rn(r, r);
+  float sp = -0x1.2d9302p-8f;
+  sp = __fmaf_rn(sp, z, 0x1.465e92p-4f);
+  sp = __fmaf_rn(sp, z, -0x1.4abbbap-1f);
+  sp = __fmaf_rn(sp, z, 0x1.921fb6p+0f);
+  float s = __fmul_rn(r, sp);
+  float c = 0x1.d99f54p-11f;
+  c = __fmaf_rn(c, z, -0x1.55c4eap-6f);
+  c = __fmaf_rn(c, z, 0x1.03c1dap-2f);
+  c = __fmaf_rn(c, z, -0x1.3bd3ccp+0f);
+  c = __fmaf_rn(c, z, 1.0f);
+  if (swap) { const float tmp = s; s = c; c = tmp; }
+  // rotate by quadrant * 90 degrees
+  const float cq = (quadrant & 1u) ? s : c;
+  const float sq = (quadrant & 1u) ? c : s;
+  const float cs = (quadrant == 1u || quadrant == 2u) ? -cq : cq;
+  const float ss = (quadrant >= 2u) ? -sq : sq;
+  g0 = __fmul_rn(rho, cs);
+  g1 = __fmul_rn(rho, ss);
+}
+
+__device__ __forceinline__ void normal_quad(uint64_t seed, uint64_t sample, uint32_t quad, float (&g)[4]) {
+  const U4 w = philox4x32_10((uint32_t)sample, (uint32_t)(sample >> 32), quad, 0u, (uint32_t)seed,
+                             (uint32_t)(seed >> 32));
+  gauss_pair(w.x, w.y, g[0], g[1]);
+  gauss_pair(w.z, w.w, g[2], g[3]);
+}
+
+template <typename T> __device__ __forceinline__ void ld4(const T* p, float (&v)[4]);
+template <> __device__ __forceinline__ void ld4<float>(const float* p, float (&v)[4]) {
+  const float4 t = *reinterpret_cast<const float4*>(p);
+  v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+}
+template <> __device__ __forceinline__ void ld4<bf16_t>(const bf16_t* p, float (&v)[4]) {
+  const uint2 t = *reinterpret_cast<const uint2*>(p);
+  v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xFFFF0000u);
+  v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xFFFF0000u);
+}
+template <typename T> __device__ __forceinline__ void st4(T* p, const float (&v)[4]);
+template <> __device__ __forceinline__ void st4<float>(float* p, const float (&v)[4]) {
+  *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+}
+template <> __device__ __forceinline__ void st4<bf16_t>(bf16_t* p, const float (&v)[4]) {
+  uint2 t;
+  t.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
+  t.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
+  *reinterpret_cast<uint2*>(p) = t;
+}
+
+// One wavefront per sample.  FLAT: the sample is a contiguous vector of n = C
+// elements with n % 4 == 0 (16-byte / 8-byte vector access).  Otherwise the sample
+// is stored [HW][C] and element i = c*HW + hw of the (c,h,w) order is gathered.
+template <typename T, bool FLAT>
+__global__ void k_pnorm_awgn(const T* __restrict__ z, T* __restrict__ y, int64_t batch, int C, int HW, int do_pnorm,
+                             int do_awgn, float sigma, uint64_t seed, uint64_t first_sample) {
+  const int lane = threadIdx.x & 63;
+  const int64_t b = (int64_t)blockIdx.x * (NT / 64) + (threadIdx.x >> 6);
+  if (b >= batch) return;
+  const int64_t n = (int64_t)C * HW;
+  const T* zb = z + b * n;
+  T* yb = y + b * n;
+  const int64_t nquads = (n + 3) >> 2;
+  float scale = 1.0f;
+  if (do_pnorm) {
+    float ss = 0.0f;
+    if (FLAT) {
+      for (int64_t q = lane; q < nquads; q += 64) {
+        float v[4];
+        ld4<T>(zb + 4 * q, v);
+        ss = fmaf(v[0], v[0], ss); ss = fmaf(v[1], v[1], ss); ss = fmaf(v[2], v[2], ss); ss = fmaf(v[3], v[3], ss);
+      }
+    } else {
+      for (int64_t i = lane; i < n; i += 64) { float v = Store<T>::ld(zb + i); ss = fmaf(v, v, ss); }
+    }
+    ss = wave_sum(ss);
+    const float ms = ss / (float)n;
+    scale = ms > 0.0f ? 1.0f / sqrtf(ms) : 0.0f;
+  }
+  const uint64_t sample = first_sample + (uint64_t)b;
+  for (int64_t q = lane; q < nquads; q += 64) {
+    float g[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (do_awgn) {
+      normal_quad(seed, sample, (uint32_t)q, g);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) g[j] = __fmul_rn(sigma, g[j]);
+    }
+    if (FLAT) {
+      float v[4];
+      ld4<T>(zb + 4 * q, v);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) v[j] = __fadd_rn(__fmul_rn(v[j], scale), g[j]);
+      st4<T>(yb + 4 * q, v);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int64_t i = 4 * q + j;
+        if (i < n) {
+          const int c = (int)(i / HW), hw = (int)(i % HW);
+          const int64_t pos = (int64_t)hw * C + c;
+          Store<T>::st(yb + pos, __fadd_rn(__fmul_rn(Store<T>::ld(zb + pos), scale), g[j]));
+        }
+      }
+    }
+  }
+}
+
+// x = z/r: dz = g/r - z * sum(g z) / (n r^3); elementwise in storage order
+template <typename T>
+__global__ void k_pnorm_bwd(const T* __restrict__ z, const T* __restrict__ g, T* __restrict__ dz, int64_t batch,
+                            int64_t n) {
+  const int lane = threadIdx.x & 63;
+  const int64_t b = (int64_t)blockIdx.x * (NT / 64) + (threadIdx.x >> 6);
+  if (b >= batch) return;
+  const T* zb = z + b * n;
+  const T* gb = g + b * n;
+  float szz = 0.0f, sgz = 0.0f;
+  for (int64_t i = lane; i < n; i += 64) {
+    const float zv = Store<T>::ld(zb + i), gv = Store<T>::ld(gb + i);
+    szz = fmaf(zv, zv, szz);
+    sgz = fmaf(gv, zv, sgz);
+  }
+  szz = wave_sum(szz);
+  sgz = wave_sum(sgz);
+  const float ms = szz / (float)n;
+  float inv_r = 0.0f, coef = 0.0f;
+  if (ms > 0.0f) {
+    inv_r = 1.0f / sqrtf(ms);
+    coef = sgz / (float)n * inv_r * inv_r * inv_r;
+  }
+  for (int64_t i = lane; i < n; i += 64) {
+    const float zv = Store<T>::ld(zb + i), gv = Store<T>::ld(gb + i);
+    Store<T>::st(dz + b * n + i, gv * inv_r - zv * coef);
+  }
+}
+
+__global__ void k_noise(uint64_t seed, uint64_t first_sample, int64_t batch, int64_t n, float* __restrict__ out) {
+  const int64_t nquads = (n + 3) >> 2;
+  const int64_t total = batch * nquads;
+  for (int64_t it = (int64_t)blockIdx.x * NT + threadIdx.x; it < total; it += (int64_t)gridDim.x * NT) {
+    const int64_t b = it / nquads, q = it % nquads;
+    float g[4];
+    normal_quad(seed, first_sample + (uint64_t)b, (uint32_t)q, g);
+    for (int j = 0; j < 4; ++j)
+      if (4 * q + j < n) out[b * n + 4 * q + j] = g[j];
+  }
+}
+
+__global__ void k_gen_bits(uint64_t seed, uint64_t first_sample, int64_t batch, int k, float* __restrict__ x) {
+  const int64_t total = batch * k;
+  for (int64_t it = (int64_t)blockIdx.x * NT + threadIdx.x; it < total; it += (int64_t)gridDim.x * NT) {
+    const int64_t b = it / k;
+    const int j = (int)(it % k);
+    const uint64_t sample = first_sample + (uint64_t)b;
+    const U4 w = philox4x32_10((uint32_t)sample, (uint32_t)(sample >> 32), (uint32_t)(j >> 7), 1u, (uint32_t)seed,
+                               (uint32_t)(seed >> 32));
+    const int wi = (j >> 5) & 3;
+    const uint32_t word = wi == 0 ? w.x : (wi == 1 ? w.y : (wi == 2 ? w.z : w.w));
+    x[it] = ((word >> (j & 31)) & 1u) ? 1.0f : -1.0f;
+  }
+}
+
+__global__ void k_count_errors(const float* __restrict__ y, const float* __restrict__ x, int64_t batch, int k,
+                               unsigned long long* bit_err, unsigned long long* blk_err) {
+  __shared__ float sm[NT / 64 + 1];
+  float be = 0.0f, ke = 0.0f;  // counts per thread are small integers: exact in binary32
+  const int64_t b = (int64_t)blockIdx.x * NT + threadIdx.x;
+  if (b < batch) {
+    int wrong = 0;
+    for (int j = 0; j < k; ++j) wrong += ((y[b * k + j] > 0.5f) != (x[b * k + j] > 0.0f)) ? 1 : 0;
+    be = (float)wrong;
+    ke = wrong ? 1.0f : 0.0f;
+  }
+  be = block_sum<NT>(be, sm);  // at most 256*k < 2^24 when k < 65536
+  ke = block_sum<NT>(ke, sm);
+  if (threadIdx.x == 0) {
+    if (be > 0.0f) atomicAdd(bit_err, (unsigned long long)be);
+    if (ke > 0.0f) atomicAdd(blk_err, (unsigned long long)ke);
+  }
+}
+
+inline int grid_for(int64_t items, int cap) {
+  int64_t g = (items + NT - 1) / NT;
+  if (g < 1) g = 1;
+  if (g > cap) g = cap;
+  return (int)g;
+}
+
+}  // namespace
+
+int launch_pnorm_awgn(const void* z, void* y, int64_t batch, int c, int hw, int dtype, int do_pnorm, int do_awgn,
+                      float sigma, uint64_t seed, uint64_t first_sample, hipStream_t s) {
+  const int64_t blocks = (batch + NT / 64 - 1) / (NT / 64);
+  if (blocks > 0x7FFFFFFF) return fail(AE_EINVAL, "pnorm_awgn: batch too large");
+  // a flat vector is a tensor with hw == 1 (or c == 1: then (c,h,w) order is storage order too)
+  int C = c, HW = hw;
+  if (C == 1) { C = HW; HW = 1; }
+  const bool flat = HW == 1 && (C % 4 == 0);
+#define LAUNCH(T, F)                                                                                              \
+  hipLaunchKernelGGL((k_pnorm_awgn<T, F>), dim3((unsigned)blocks), dim3(NT), 0, s, (const T*)z, (T*)y, batch, C, HW, \
+                     do_pnorm, do_awgn, sigma, seed, first_sample)
+  if (dtype == AE_BF16) { if (flat) LAUNCH(bf16_t, true); else LAUNCH(bf16_t, false); }
+  else { if (flat) LAUNCH(float, true); else LAUNCH(float, false); }
+#undef LAUNCH
+  return launch_status("pnorm_awgn");
+}
+
+int launch_pnorm_bwd(const void* z, const void* g, void* dz, int64_t batch, int64_t n, int dtype, hipStream_t s) {
+  const int64_t blocks = (batch + NT / 64 - 1) / (NT / 64);
+  if (dtype == AE_BF16)
+    hipLaunchKernelGGL((k_pnorm_bwd<bf16_t>), dim3((unsigned)blocks), dim3(NT), 0, s, (const bf16_t*)z, (const bf16_t*)g,
+                       (bf16_t*)dz, batch, n);
+  else
+    hipLaunchKernelGGL((k_pnorm_bwd<float>), dim3((unsigned)blocks), dim3(NT), 0, s, (const float*)z, (const float*)g,
+                       (float*)dz, batch, n);
+  return launch_status("pnorm_bwd");
+}
+
+int launch_noise(uint64_t seed, uint64_t first_sample, int64_t batch, int64_t n, float* out, hipStream_t s) {
+  hipLaunchKernelGGL(k_noise, dim3(grid_for(batch * ((n + 3) / 4), 1 << 20)), dim3(NT), 0, s, seed, first_sample, batch,
+                     n, out);
+  return launch_status("noise");
+}
+
+int launch_gen_bits(uint64_t seed, uint64_t first_sample, int64_t batch, int k, float* x, hipStream_t s) {
+  hipLaunchKernelGGL(k_gen_bits, dim3(grid_for(batch * k, 1 << 20)), dim3(NT), 0, s, seed, first_sample, batch, k, x);
+  return launch_status("gen_bits");
+}
+
+int launch_count_errors(const float* y, const float* x, int64_t batch, int k, uint64_t* bit_err, uint64_t* blk_err,
+                        hipStream_t s) {
+  if (k >= 65536) return fail(AE_EINVAL, "count_errors: k must be below 65536");
+  hipLaunchKernelGGL(k_count_errors, dim3((unsigned)((batch + NT - 1) / NT)), dim3(NT), 0, s, y, x, batch, k,
+                     (unsigned long long*)bit_err, (unsigned long long*)blk_err);
+  return launch_status("count_errors");
+}
+
+}  // namespace ae

@@ -1,0 +1,130 @@
+"""Helpers of the GPU parity tests: run the same seeded case through the HIP library
+(via its C boundary) and through the CPU oracle, and compare tensor by tensor."""
+import numpy as np
+
+import oracle.ae_oracle as orc
+import workloads as wl
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def rel_errors(a, o):
+    """(relative L2 error, max error relative to the largest reference magnitude)."""
+    a = np.asarray(a, dtype=np.float64).ravel()
+    o = np.asarray(o, dtype=np.float64).ravel()
+    assert a.shape == o.shape, (a.shape, o.shape)
+    assert np.all(np.isfinite(a))
+    n2 = np.linalg.norm(o)
+    mx = np.abs(o).max() if o.size else 0.0
+    d = a - o
+    l2 = np.linalg.norm(d) / n2 if n2 > 0 else np.linalg.norm(d)
+    lm = np.abs(d).max() / mx if mx > 0 else (np.abs(d).max() if d.size else 0.0)
+    return float(l2), float(lm)
+
+
+STRICT = True   # set False (debugging only) to collect errors instead of asserting
+
+
+def assert_close(a, o, tol, what):
+    l2, lm = rel_errors(a, o)
+    if STRICT:
+        assert l2 <= tol and lm <= tol, "%s: rel L2 %.3e, rel max %.3e (tol %.1e)" % (what, l2, lm, tol)
+    return l2, lm
+
+
+def to_dev(a, dtype, torch):
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    return t.to(torch.bfloat16).contiguous() if dtype == "bf16" else t
+
+
+def run_case(spec, batch, dtype="f32", seed=0, snr_db=10.0, first_sample=0, bn_mode=0, backward=True,
+             perturb=True, check_acts=True, x=None, params=None, cot=None, grad_tol=None, grad_cos=None):
+    """Run spec on both sides; assert parity of y, every saved activation and (optionally)
+    every gradient.  Returns a dict of the worst errors.
+
+    fp32 models: everything against the plain oracle at 1e-4.
+    bf16 models: y and activations against the plain (real-number) oracle at 2e-2, and again
+    against the oracle emulating the bfloat16 storage format; gradients against the emulating
+    oracle, so that ReLU masks and max-pool winners are decided in the format's precision on
+    both sides.  grad_tol / grad_cos override the gradient bar (deep bf16 networks: see
+    DEEP_BF16_GRAD)."""
+    import torch
+    from paper_2602_17681_amd import binding as ae
+
+    bf = dtype == "bf16"
+    tol = TOL[dtype]
+    gtol = tol if grad_tol is None else grad_tol
+    if params is None:
+        params = wl.make_params(spec, seed, bn_mode=bn_mode, perturb=perturb, bf16=bf)
+    if x is None:
+        x = wl.make_input(spec, batch, seed, bf16=bf)
+    refs = [("plain", orc.Net(spec, batch, bn_mode))]
+    if bf:
+        refs.append(("bf16-storage", orc.Net(spec, batch, bn_mode, store_bf16=True)))
+    y_refs = [net.forward(params, x, snr_db=snr_db, seed=seed, first_sample=first_sample) for _, net in refs]
+    net = refs[-1][1]            # the one gradients are compared with
+
+    m = ae.Model(spec, batch, ae.DTYPES[dtype], bn_mode)
+    assert m.n_params == net.n_params and m.in_shape == net.in_shape and m.out_shape == net.out_shape
+    p_d = torch.from_numpy(params).cuda()
+    x_d = to_dev(x, dtype, torch)
+    y_d = torch.empty((batch,) + m.out_shape, dtype=m.tdtype, device="cuda")
+    m.model_set_sample_offset(first_sample)
+    m.model_forward(p_d, x_d, snr_db, seed, y_d)
+    torch.cuda.synchronize()
+    worst = {}
+    y_gpu = y_d.float().cpu().numpy()
+    for (rname, _), y_ref in zip(refs, y_refs):
+        worst["y/" + rname] = assert_close(y_gpu, y_ref, tol, "y vs %s oracle" % rname)
+    if check_acts:
+        ns = m.model_num_steps()
+        for s in range(ns):
+            tok, chw = m.model_step_info(s)
+            if s == ns - 1 and chw == m.out_shape and tok == net.n_ops - 1:
+                continue  # the boundary layout step: its output is y itself
+            buf = torch.empty((batch,) + chw, dtype=torch.float32, device="cuda")
+            m.model_get_activation(s, buf)
+            torch.cuda.synchronize()
+            got = buf.cpu().numpy()
+            for rname, rnet in refs:
+                ref = rnet.activation(tok).reshape((batch,) + chw)
+                worst["act%d/%s" % (s, rname)] = assert_close(
+                    got, ref, tol, "activation of step %d (token %d) vs %s oracle" % (s, tok, rname))
+    if backward:
+        if cot is None:
+            cot = wl.make_cotangent((batch,) + m.out_shape, seed, bf16=bf)
+        g_ref, _ = net.backward(params, cot.astype(np.float64))
+        dy_d = to_dev(cot, dtype, torch)
+        g_d = torch.full((m.n_params,), float("nan"), dtype=torch.float32, device="cuda")
+        m.model_backward(p_d, x_d, dy_d, g_d)
+        torch.cuda.synchronize()
+        g = g_d.cpu().numpy()
+        assert np.all(np.isfinite(g))
+        ent, _, _, _ = wl.param_layout(spec, bn_mode)
+        for e in ent:
+            sz = int(np.prod(e["shape"]))
+            sl = slice(e["offset"], e["offset"] + sz)
+            name = "grad %s.%s@%d" % (e["name"], e["kind"], e["op"])
+            if np.abs(g_ref[sl]).max() == 0.0:
+                assert np.abs(g[sl]).max() == 0.0, name
+                continue
+            if e["kind"] == "b" and _feeds_batch_bn(spec, e["op"], bn_mode):
+                # analytically zero: compare against the scale of the layer's weight gradient instead
+                wsl = [q for q in ent if q["op"] == e["op"] and q["kind"] == "w"][0]
+                scale = np.abs(g_ref[wsl["offset"]:wsl["offset"] + int(np.prod(wsl["shape"]))]).max()
+                if STRICT:
+                    assert np.abs(g[sl]).max() <= max(gtol, 1e-3) * scale * 10, name
+                continue
+            worst[name] = assert_close(g[sl], g_ref[sl], gtol, name)
+            if grad_cos is not None and sz >= 16:
+                c = float(np.dot(g[sl], g_ref[sl]) / (np.linalg.norm(g[sl]) * np.linalg.norm(g_ref[sl])))
+                worst[name] = worst[name] + (c,)
+                if STRICT:
+                    assert c >= grad_cos, "%s: cosine %.4f < %.4f" % (name, c, grad_cos)
+    m.close()
+    return worst
+
+
+def _feeds_batch_bn(spec, op, bn_mode):
+    toks = [t.strip() for t in spec.split(",")][1:]
+    return bn_mode == 0 and op + 1 < len(toks) and toks[op + 1] == "bn"

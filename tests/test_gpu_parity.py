@@ -1,0 +1,236 @@
+"""GPU parity tests: the HIP library, called through its C boundary, against the CPU
+oracle on the same seeded inputs.  Integer / bit work must match exactly; floating
+point within 1e-4 (fp32) or 2e-2 (bf16) in relative L2 and relative max norm."""
+import numpy as np
+import pytest
+
+import oracle.ae_oracle as orc
+import workloads as wl
+from parity_util import TOL, assert_close, rel_errors, run_case, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ae():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_2602_17681_amd import binding
+    return binding
+
+
+# ------------------------------------------------------------------ noise: bit exact
+@pytest.mark.parametrize("seed,first,batch,n", [
+    (0, 0, 64, 64), (3, 65536 * 7, 1024, 128), (0x123456789ABCDEF, (1 << 32) - 5, 11, 37),
+    (4, 0, 32, 4096), (99, 1 << 40, 3, 1), (7, 12345, 257, 1026), (11, 0, 1, 4_000_000)])
+def test_noise_bit_exact(ae, seed, first, batch, n):
+    import torch
+    out = torch.empty((batch, n), dtype=torch.float32, device="cuda")
+    ae.model_noise(seed, first, batch, n, out)
+    torch.cuda.synchronize()
+    ref = orc.noise(seed, first, batch, n)
+    got = out.cpu().numpy()
+    assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))
+
+
+def test_gen_bits_bit_exact_and_count_errors(ae):
+    import torch
+    seed, first, B, K = 3, 65536 * 3 + 17, 4099, 64
+    x = torch.empty((B, K), dtype=torch.float32, device="cuda")
+    ae.model_gen_bits(seed, first, B, K, x)
+    ref = orc.gen_bits(seed, first, B, K)
+    assert np.array_equal(x.cpu().numpy(), ref)
+    K2 = 200
+    x2 = torch.empty((33, K2), dtype=torch.float32, device="cuda")
+    ae.model_gen_bits(seed, 5, 33, K2, x2)
+    assert np.array_equal(x2.cpu().numpy(), orc.gen_bits(seed, 5, 33, K2))
+    rng = np.random.default_rng(0)
+    y = np.clip((ref > 0) * 1.0 + 0.45 * rng.standard_normal((B, K)), 0, 1).astype(np.float32)
+    y[0, 0] = 0.5
+    be = torch.zeros(1, dtype=torch.int64, device="cuda")
+    ke = torch.zeros(1, dtype=torch.int64, device="cuda")
+    yd = torch.from_numpy(y).cuda()
+    ae.model_count_errors(yd, x, B, K, be, ke)
+    ae.model_count_errors(yd, x, B, K, be, ke)      # counters accumulate
+    rb, rk = orc.count_errors(y, ref)
+    assert (int(be.item()), int(ke.item())) == (2 * rb, 2 * rk)
+
+
+# ------------------------------------------------------------------ channel kernel alone
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("batch,n", [(1000, 128), (64, 64), (7, 4096), (5, 1024), (3, 36)])
+def test_pnorm_awgn_standalone(ae, dtype, batch, n):
+    import torch
+    rng = np.random.default_rng(n)
+    z = rng.standard_normal((batch, n)).astype(np.float32) * 3.0
+    z[1] = 0.0          # all-zero sample: output is pure noise
+    if dtype == "bf16":
+        z = wl.round_to_bf16(z)
+    zd = to_dev(z, dtype, torch)
+    yd = torch.empty_like(zd)
+    ae.model_pnorm_awgn(zd, yd, batch, n, 5.0, 42, 1000)
+    net = orc.Net("in:%dx1x1,pnorm,awgn" % n, batch)
+    ref = net.forward(np.zeros(0, np.float32), z.reshape(batch, n, 1, 1), snr_db=5.0, seed=42, first_sample=1000)
+    got = yd.float().cpu().numpy()
+    assert_close(got, ref.reshape(batch, n), TOL[dtype] if dtype == "bf16" else 2e-6, "pnorm_awgn")
+    if dtype == "f32":
+        sig = np.float32(orc.sigma(5.0))
+        assert np.array_equal(got[1], sig * orc.noise(42, 1000, batch, n)[1])
+        pw = ((got - (sig * orc.noise(42, 1000, batch, n)).astype(np.float64)) ** 2).mean(axis=1)
+        np.testing.assert_allclose(np.delete(pw, 1), 1.0, atol=1e-5)
+
+
+# ------------------------------------------------------------------ small networks, every op pattern
+SMALL = [
+    # conv+bn+relu+pool encoder, fc latent, fc + upsampling conv decoder (several tiles, ragged sizes)
+    ("in:3x12x20,conv3:8,bn,relu,pool2,conv3:12,bn,relu,pool2,flatten,fc:24,pnorm,awgn,fc:180,reshape:12x3x5,"
+     "up2,conv3:8,relu,up2,conv3:3,sigmoid", 5),
+    # single-channel image, conv1 latent map
+    ("in:1x8x8,conv3:4,bn,relu,pool2,conv1:6,pnorm,awgn,conv1:4,up2,conv3:1,sigmoid", 7),
+    # fully connected chain
+    ("in:10x1x1,fc:33,relu,fc:16,pnorm,awgn,fc:20,relu,fc:10,sigmoid", 67),
+    # patterns outside the benchmark configs: bn without pool, pool without bn, sigmoid+bn, awgn alone
+    ("in:2x8x8,conv3:5,bn,sigmoid,conv3:4,relu,pool2,conv1:3,bn,awgn,up2,conv3:2", 3),
+    # channel counts that are multiples of the vector widths
+    ("in:4x8x8,conv3:16,bn,relu,pool2,conv3:32,bn,relu,pool2,flatten,fc:64,pnorm,awgn,fc:128,reshape:32x2x2,"
+     "up2,conv3:16,relu,up2,conv3:8,sigmoid", 6),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", range(len(SMALL)))
+def test_small_networks_forward_backward(ae, case, dtype):
+    spec, batch = SMALL[case]
+    run_case(spec, batch, dtype=dtype, seed=100 + case, snr_db=7.0, first_sample=3)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_stored_statistics_batch_norm(ae, dtype):
+    run_case("in:3x8x8,conv3:8,bn,relu,pool2,conv1:4,sigmoid", 4, dtype=dtype, seed=5, bn_mode=1)
+
+
+def test_sample_offset_partition_invariance(ae):
+    """Two launches of B/2 with offsets give the same outputs as one launch of B (no batch-norm here)."""
+    import torch
+    spec = "in:6x1x1,fc:16,relu,fc:8,pnorm,awgn,fc:16,relu,fc:6,sigmoid"
+    B = 64
+    params = wl.make_params(spec, 1, perturb=True)
+    x = wl.make_input(spec, B, 1)
+    pd = torch.from_numpy(params).cuda()
+    full = ae.Model(spec, B)
+    yf = torch.empty((B, 6, 1, 1), device="cuda")
+    full.model_set_sample_offset(1000)
+    full.model_forward(pd, torch.from_numpy(x).cuda(), 3.0, 9, yf)
+    half = ae.Model(spec, B // 2)
+    ys = []
+    for i in range(2):
+        yh = torch.empty((B // 2, 6, 1, 1), device="cuda")
+        half.model_set_sample_offset(1000 + i * (B // 2))
+        half.model_forward(pd, torch.from_numpy(x[i * (B // 2):(i + 1) * (B // 2)]).cuda(), 3.0, 9, yh)
+        ys.append(yh)
+    assert torch.equal(torch.cat(ys), yf)
+
+
+# ------------------------------------------------------------------ loss
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("n", [1, 1000, 3 * 32 * 32 * 17 + 5])
+def test_loss_mse(ae, dtype, n):
+    import torch
+    rng = np.random.default_rng(n)
+    y = rng.random(n).astype(np.float32)
+    t = rng.random(n).astype(np.float32)
+    if dtype == "bf16":
+        y, t = wl.round_to_bf16(y), wl.round_to_bf16(t)
+    yd, td = to_dev(y, dtype, torch), to_dev(t, dtype, torch)
+    loss = torch.full((1,), 123.0, device="cuda")
+    dy = torch.empty_like(yd)
+    ae.model_loss_mse(yd, td, loss, dy)
+    ref, dref = orc.loss_mse(y, t)
+    assert abs(loss.item() - ref) <= 1e-5 * ref + 1e-12
+    assert_close(dy.float().cpu().numpy(), dref, 1e-6 if dtype == "f32" else 5e-3, "dy")
+    ae.model_loss_mse(yd, td, loss, None)      # overwrites, does not accumulate
+    assert abs(loss.item() - ref) <= 1e-5 * ref + 1e-12
+
+
+# ------------------------------------------------------------------ benchmark configurations
+def test_cfg1_full_forward(ae):
+    cfg = wl.CONFIGS["cfg1"]
+    run_case(cfg["spec"], cfg["batch"], dtype="f32", seed=cfg["seed"], snr_db=10.0, backward=False, perturb=False)
+
+
+def test_cfg1_forward_backward_perturbed(ae):
+    cfg = wl.CONFIGS["cfg1"]
+    run_case(cfg["spec"], 16, dtype="f32", seed=cfg["seed"], snr_db=10.0, backward=True, perturb=True)
+
+
+@pytest.mark.parametrize("snr_db", [0.0, 20.0])
+def test_cfg2_reduced_resolution(ae, snr_db):
+    spec = wl.scaled_spec("cfg2", 16)
+    run_case(spec, 12, dtype="f32", seed=1, snr_db=snr_db)
+
+
+def test_cfg3_reduced_resolution_bf16(ae):
+    spec = wl.scaled_spec("cfg3", 16)
+    run_case(spec, 6, dtype="bf16", seed=2, snr_db=5.0)
+
+
+def test_cfg4_launch_and_error_counts(ae):
+    import torch
+    cfg = wl.CONFIGS["cfg4"]
+    B, K = 8192, 64
+    first = 65536 * 5
+    spec = cfg["spec"]
+    params = wl.make_params(spec, cfg["seed"])
+    m = ae.Model(spec, B)
+    pd = torch.from_numpy(params).cuda()
+    x = torch.empty((B, K, 1, 1), device="cuda")
+    y = torch.empty((B, K, 1, 1), device="cuda")
+    be = torch.zeros(1, dtype=torch.int64, device="cuda")
+    ke = torch.zeros(1, dtype=torch.int64, device="cuda")
+    ae.model_gen_bits(cfg["seed"], first, B, K, x)
+    m.model_set_sample_offset(first)
+    m.model_forward(pd, x, 2.0, cfg["seed"], y)
+    ae.model_count_errors(y, x, B, K, be, ke)
+    xr = orc.gen_bits(cfg["seed"], first, B, K)
+    assert np.array_equal(x.cpu().numpy().reshape(B, K), xr)
+    net = orc.Net(spec, B)
+    yr = net.forward(params, xr.reshape(B, K, 1, 1), snr_db=2.0, seed=cfg["seed"], first_sample=first)
+    assert_close(y.cpu().numpy(), yr, 1e-4, "cfg4 y")
+    # decisions agree except where the reference output sits within rounding of the threshold
+    yg = y.cpu().numpy().reshape(B, K)
+    yo = yr.reshape(B, K)
+    near = np.abs(yo - 0.5) < 1e-4
+    assert near.mean() < 1e-3
+    assert np.array_equal((yg > 0.5)[~near], (yo > 0.5)[~near])
+    rb, rk = orc.count_errors(yg.astype(np.float64), xr)     # counting itself is exact
+    assert (int(be.item()), int(ke.item())) == (rb, rk)
+    ob, _ = orc.count_errors(yo, xr)
+    assert abs(rb - ob) <= int(near.sum())
+
+
+def test_cfg5_reduced_resolution_bf16(ae):
+    spec = wl.scaled_spec("cfg5", 32)
+    run_case(spec, 4, dtype="bf16", seed=4, snr_db=10.0)
+
+
+# ------------------------------------------------------------------ error handling (host side, no kernel faults)
+def test_error_codes(ae):
+    import torch
+    with pytest.raises(ae.AeError) as e:
+        ae.Model("in:3x4x4,relu", 2)
+    assert e.value.code == -2
+    with pytest.raises(ae.AeError) as e:
+        ae.Model("in:3x5x5,conv3:4,pool2", 2)
+    assert e.value.code == -3
+    with pytest.raises(ae.AeError) as e:
+        ae.Model("in:3x4x4,conv3:4", 0)
+    assert e.value.code == -1
+    m = ae.Model("in:3x4x4,conv3:4", 2)
+    p = torch.zeros(m.n_params, device="cuda")
+    x = torch.zeros((2, 3, 4, 4), device="cuda")
+    g = torch.zeros(m.n_params, device="cuda")
+    with pytest.raises(ae.AeError) as e:
+        m.model_backward(p, x, torch.zeros((2, 4, 4, 4), device="cuda"), g)
+    assert e.value.code == -4
+    assert ae.lib.model_forward(m._h, None, None, 1.0, 0, None, None) == -1
+    assert "null" in ae.model_last_error()

@@ -460,3 +460,33 @@ def test_spec_shapes_and_param_counts():
 def test_bad_specs_rejected(bad):
     with pytest.raises(ValueError):
         orc.Net(bad, 2)
+
+
+# ------------------------------------------------------------------ bfloat16 storage emulation
+def test_store_bf16_rounding_points_and_values():
+    """With store_bf16 the stored tensors are bfloat16-representable and equal to the rounded
+    plain results; tensors the format never stores (inside a bn/relu/pool run) are not rounded."""
+    spec = "in:3x8x8,conv3:4,bn,relu,pool2,conv1:2,sigmoid"
+    B = 3
+    params = wl.make_params(spec, 40, perturb=True, bf16=True)
+    x = wl.make_input(spec, B, 40, bf16=True)
+    plain = orc.Net(spec, B)
+    plain.forward(params, x)
+    emu = orc.Net(spec, B, store_bf16=True)
+    emu.forward(params, x)
+
+    def is_bf16(a):
+        a32 = a.astype(np.float32)
+        return np.array_equal(a32.astype(np.float64), a) and np.array_equal(wl.round_to_bf16(a32), a32)
+
+    conv = emu.activation(0)
+    assert is_bf16(conv)
+    np.testing.assert_array_equal(conv, wl.round_to_bf16(plain.activation(0).astype(np.float32)).astype(np.float64))
+    assert not is_bf16(emu.activation(1))            # bn output lives in registers only
+    assert is_bf16(emu.activation(3))                # end of the bn/relu/pool run
+    assert is_bf16(emu.activation(4)) and is_bf16(emu.activation(5))
+    # ties-to-even and sign handling of the rounding itself, against the integer recipe
+    v = np.array([1.00390625, 1.01171875, -1.00390625, 3.0e-5, 65280.0, 0.0, 1.0 + 2 ** -8 + 2 ** -20], np.float32)
+    n = orc.Net("in:%dx1x1,relu" % v.size, 1, store_bf16=True)     # relu output is stored
+    out = n.forward(np.zeros(0, np.float32), np.abs(v).reshape(1, -1, 1, 1)).ravel()
+    np.testing.assert_array_equal(out, wl.round_to_bf16(np.abs(v)).astype(np.float64))
