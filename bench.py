@@ -1,0 +1,202 @@
+#!/usr/bin/env python3
+"""Benchmark of the autoencoder-over-AWGN hot path on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic batch of the chosen
+workload: forward (+ MSE loss + backward where the workload trains; + message bits and
+error counting for the Monte-Carlo workload).  Inputs, parameters and outputs are
+resident in HBM before the timed region.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg5] [--no-cpu-baseline] [--no-per-config]
+"""
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+
+import workloads as wl
+
+PEAK = {"bf16": 2500.0, "f32": 157.3}     # dense MFMA TFLOP/s, MI355X
+HBM_PEAK_GBS = 8000.0
+
+
+def build_case(name, torch, ae, batch=None):
+    cfg = wl.CONFIGS[name]
+    bf = cfg["dtype"] == "bf16"
+    B = batch or cfg["batch"]
+    m = ae.Model(cfg["spec"], B, ae.DTYPES[cfg["dtype"]])
+    params = torch.from_numpy(wl.make_params(cfg["spec"], cfg["seed"], bf16=bf)).cuda()
+    if name == "cfg4":
+        x = torch.empty((B,) + m.in_shape, dtype=torch.float32, device="cuda")
+    else:
+        x = torch.from_numpy(wl.make_input(cfg["spec"], B, cfg["seed"], bf16=bf)).cuda().to(m.tdtype).contiguous()
+    st = dict(cfg=cfg, name=name, m=m, params=params, x=x, B=B,
+              y=torch.empty((B,) + m.out_shape, dtype=m.tdtype, device="cuda"))
+    if cfg["backward"]:
+        st["dy"] = torch.empty_like(st["y"])
+        st["grads"] = torch.empty(m.n_params, dtype=torch.float32, device="cuda")
+        st["loss"] = torch.zeros(1, dtype=torch.float32, device="cuda")
+    if name == "cfg4":
+        st["bit_err"] = torch.zeros(1, dtype=torch.int64, device="cuda")
+        st["blk_err"] = torch.zeros(1, dtype=torch.int64, device="cuda")
+    st["i"] = 0
+    return st
+
+
+def one_step(st, ae):
+    cfg, m = st["cfg"], st["m"]
+    snr = cfg["snr_db"][st["i"] % len(cfg["snr_db"])]
+    if st["name"] == "cfg4":
+        first = st["i"] * st["B"]
+        ae.model_gen_bits(cfg["seed"], first, st["B"], m.in_shape[0], st["x"])
+        m.model_set_sample_offset(first)
+        m.model_forward(st["params"], st["x"], snr, cfg["seed"], st["y"])
+        ae.model_count_errors(st["y"], st["x"], st["B"], m.in_shape[0], st["bit_err"], st["blk_err"])
+    else:
+        m.model_set_sample_offset(st["i"] * st["B"])
+        m.model_forward(st["params"], st["x"], snr, cfg["seed"], st["y"])
+        if cfg["backward"]:
+            ae.model_loss_mse(st["y"], st["x"], st["loss"], st["dy"])
+            m.model_backward(st["params"], st["x"], st["dy"], st["grads"])
+    st["i"] += 1
+
+
+def run_timed(st, ae, torch, steps, warmup, timing=False):
+    for _ in range(warmup):
+        one_step(st, ae)
+    torch.cuda.synchronize()
+    st["m"].model_timing_reset()
+    st["m"].model_timing_enable(timing)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        one_step(st, ae)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    st["m"].model_timing_enable(False)
+    return dt
+
+
+def kernel_table(st, steps):
+    rows = []
+    for s in st["m"].model_timing_read():
+        if s["launches"] == 0:
+            continue
+        avg_ms = s["total_ms"] / s["launches"]
+        rows.append(dict(name=s["name"], avg_ms=avg_ms, ms_per_step=s["total_ms"] / steps,
+                         tflops=(s["flops"] / avg_ms / 1e9) if s["flops"] > 0 and avg_ms > 0 else None,
+                         gbs=(s["bytes"] / avg_ms / 1e6) if s["bytes"] > 0 and avg_ms > 0 else None,
+                         flops=s["flops"], bytes=s["bytes"]))
+    return rows
+
+
+def roofline_of(rows, dtype):
+    """The kernel launch that takes the most time per step, priced against the roof that bounds it."""
+    if not rows:
+        return None
+    top = max(rows, key=lambda r: r["ms_per_step"])
+    if top["flops"] > 0:
+        # machine balance decides: a conv launch whose arithmetic intensity is below peak_flops/peak_bw is HBM-bound
+        ai = top["flops"] / max(top["bytes"], 1.0)
+        balance = PEAK[dtype] * 1e12 / (HBM_PEAK_GBS * 1e9)
+        if ai >= balance:
+            return dict(bound="mfma", kernel=top["name"], achieved=top["tflops"], peak=PEAK[dtype], unit="TFLOP/s",
+                        frac=top["tflops"] / PEAK[dtype], traffic=None, avg_ms=top["avg_ms"])
+    return dict(bound="hbm", kernel=top["name"], achieved=top["gbs"], peak=HBM_PEAK_GBS, unit="GB/s",
+                frac=(top["gbs"] or 0.0) / HBM_PEAK_GBS, traffic=None, avg_ms=top["avg_ms"])
+
+
+def cpu_baseline(name, budget_s=20.0):
+    """The oracle as it stands, on a bounded sample of the same workload (same layer list and
+    resolution, smaller batch), timed on this machine's host cores."""
+    import oracle.ae_oracle as orc
+    cfg = wl.CONFIGS[name]
+    sample = {"cfg1": 64, "cfg2": 8, "cfg3": 4, "cfg4": 4096, "cfg5": 1}[name]
+    spec = cfg["spec"]
+    bf = cfg["dtype"] == "bf16"
+    params = wl.make_params(spec, cfg["seed"], bf16=bf)
+    if name == "cfg4":
+        x = orc.gen_bits(cfg["seed"], 0, sample, 64).reshape(sample, 64, 1, 1)
+    else:
+        x = wl.make_input(spec, sample, cfg["seed"], bf16=bf)
+    net = orc.Net(spec, sample)
+    t0 = time.perf_counter()
+    y = net.forward(params, x, snr_db=cfg["snr_db"][0], seed=cfg["seed"])
+    if cfg["backward"]:
+        _, dy = orc.loss_mse(y, x.astype(np.float64))
+        net.backward(params, dy)
+    elif name == "cfg4":
+        orc.count_errors(y.reshape(sample, 64), x.reshape(sample, 64))
+    dt = time.perf_counter() - t0
+    return dict(value=sample / dt, unit="samples/s", cores=orc.num_threads(), kind="oracle",
+                sample="batch %d of %s (%s), one step in %.1f s" % (
+                    sample, name, "forward+loss+backward" if cfg["backward"] else "forward", dt))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="cfg5", choices=sorted(wl.CONFIGS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-per-config", action="store_true")
+    ap.add_argument("--kernels", action="store_true", help="also print the per-kernel table to stderr")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives): use --gpus 1")
+
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the HIP library is the only implementation (no CPU fallback)")
+    from paper_2602_17681_amd import binding as ae
+
+    name = args.config
+    cfg = wl.CONFIGS[name]
+    st = build_case(name, torch, ae)
+    # timed region: exactly `steps` steps, per-kernel HIP events recorded on the same stream
+    dt = run_timed(st, ae, torch, args.steps, args.warmup, timing=True)
+    rows = kernel_table(st, args.steps)
+    value = st["B"] * args.steps / dt
+    if args.kernels:
+        for r in sorted(rows, key=lambda r: -r["ms_per_step"]):
+            print("%-34s %9.4f ms/step  avg %9.4f ms  %s  %s" % (
+                r["name"], r["ms_per_step"], r["avg_ms"],
+                ("%8.1f TFLOP/s" % r["tflops"]) if r["tflops"] else " " * 15,
+                ("%8.1f GB/s" % r["gbs"]) if r["gbs"] else ""), file=sys.stderr)
+    out = {
+        "metric": "samples/sec, forward%s" % ("+loss+backward" if cfg["backward"] else ""),
+        "value": value, "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg["dtype"], "data": "synthetic",
+        "config": {"workload": "%s: %s" % (name, cfg["spec"]), "batch": st["B"], "snr_db": cfg["snr_db"],
+                   "seed": cfg["seed"], "pass": "forward+loss+backward" if cfg["backward"] else "forward"},
+        "roofline": roofline_of(rows, cfg["dtype"]),
+        "kernels": [dict(name=r["name"], ms_per_step=round(r["ms_per_step"], 5),
+                         tflops=None if r["tflops"] is None else round(r["tflops"], 2),
+                         gbs=None if r["gbs"] is None else round(r["gbs"], 1))
+                    for r in sorted(rows, key=lambda r: -r["ms_per_step"])[:12]],
+    }
+    st["m"].close()
+    del st
+    if not args.no_per_config:
+        per = {}
+        for other in sorted(wl.CONFIGS):
+            if other == name:
+                per[other] = dict(samples_per_s=value, ms_per_step=dt / args.steps * 1e3)
+                continue
+            torch.cuda.empty_cache()
+            s2 = build_case(other, torch, ae)
+            k2 = max(3, min(args.steps, 10))
+            d2 = run_timed(s2, ae, torch, k2, 2)
+            per[other] = dict(samples_per_s=s2["B"] * k2 / d2, ms_per_step=d2 / k2 * 1e3)
+            s2["m"].close()
+            del s2
+        out["per_config"] = per
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(name)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

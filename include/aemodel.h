@@ -156,6 +156,19 @@ int model_num_steps(const ae_model* m, int* n_steps);
 int model_step_info(const ae_model* m, int step, int* last_token, int64_t chw[3]);
 int model_get_activation(ae_model* m, int step, float* out_nchw, void* stream);
 
+/* Per-kernel timing for benchmarks.  While enabled, every kernel the executor
+ * launches is bracketed by two HIP events on the caller's stream (a few
+ * microseconds of host time per launch).  Slots are named
+ * "stepNN.<fwd|bwd>.<kernel>"; model_timing_read waits for the slot's events,
+ * adds their elapsed times to the slot's total and reports the algorithmic
+ * floating-point operations and bytes of one launch (2*M*N*K for the convolution
+ * family; bytes every operand must cross HBM at least once).  name may be NULL. */
+int model_timing_enable(ae_model* m, int on);
+int model_timing_slots(const ae_model* m, int* n_slots);
+int model_timing_read(ae_model* m, int slot, char* name, int name_len, double* total_ms, int64_t* launches,
+                      double* flops_per_launch, double* bytes_per_launch);
+int model_timing_reset(ae_model* m);
+
 const char* model_last_error(void);
 
 #ifdef __cplusplus

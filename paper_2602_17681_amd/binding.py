@@ -22,7 +22,8 @@ SYMBOLS = [
     "model_describe", "model_create", "model_destroy", "model_param_count", "model_io_shape",
     "model_set_sample_offset", "model_forward", "model_backward", "model_loss_mse", "model_noise",
     "model_pnorm_awgn", "model_gen_bits", "model_count_errors", "model_num_steps", "model_step_info",
-    "model_get_activation", "model_last_error",
+    "model_get_activation", "model_timing_enable", "model_timing_slots", "model_timing_read", "model_timing_reset",
+    "model_last_error",
 ]
 
 
@@ -55,6 +56,11 @@ def _load():
     L.model_num_steps.argtypes = [vp, C.POINTER(C.c_int)]
     L.model_step_info.argtypes = [vp, C.c_int, C.POINTER(C.c_int), i64p]
     L.model_get_activation.argtypes = [vp, C.c_int, vp, vp]
+    L.model_timing_enable.argtypes = [vp, C.c_int]
+    L.model_timing_slots.argtypes = [vp, C.POINTER(C.c_int)]
+    L.model_timing_read.argtypes = [vp, C.c_int, C.c_char_p, C.c_int, C.POINTER(C.c_double), i64p,
+                                    C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    L.model_timing_reset.argtypes = [vp]
     L.model_last_error.restype = C.c_char_p
     for name in SYMBOLS:
         if name not in ("model_destroy", "model_last_error"):
@@ -147,6 +153,28 @@ class Model:
         chw = (C.c_int64 * 3)()
         _check(lib.model_step_info(self._h, step, C.byref(tok), chw))
         return tok.value, tuple(chw)
+
+    def model_timing_enable(self, on):
+        _check(lib.model_timing_enable(self._h, 1 if on else 0))
+
+    def model_timing_reset(self):
+        _check(lib.model_timing_reset(self._h))
+
+    def model_timing_read(self):
+        """List of dicts {name, total_ms, launches, flops, bytes} (waits for the recorded events)."""
+        n = C.c_int()
+        _check(lib.model_timing_slots(self._h, C.byref(n)))
+        out = []
+        for i in range(n.value):
+            name = C.create_string_buffer(96)
+            ms = C.c_double()
+            cnt = C.c_int64()
+            fl = C.c_double()
+            by = C.c_double()
+            _check(lib.model_timing_read(self._h, i, name, 96, C.byref(ms), C.byref(cnt), C.byref(fl), C.byref(by)))
+            out.append(dict(name=name.value.decode(), total_ms=ms.value, launches=cnt.value, flops=fl.value,
+                            bytes=by.value))
+        return out
 
     def model_get_activation(self, step, out_nchw):
         _check(lib.model_get_activation(self._h, step, _ptr(out_nchw, torch.float32), _stream()))

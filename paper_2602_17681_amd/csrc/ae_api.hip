@@ -1,14 +1,34 @@
 // ae_api.hip — the exported C functions: model lifetime, and the host-side
 // executor that walks the plan and enqueues one kernel sequence per step.
 #include <math.h>
+#include <stdio.h>
 #include <string.h>
 
+#include <map>
 #include <new>
+#include <string>
+#include <utility>
+#include <vector>
 
 #include "ae_internal.h"
 
+// Optional per-kernel timing: when enabled, every kernel launch of the executor is
+// bracketed by two HIP events on the caller's stream; model_timing_read turns the
+// pairs into accumulated milliseconds.  Slots are keyed by "<step>.<phase>.<kernel>".
+struct TimeSlot {
+  std::string name;
+  double flops = 0.0, bytes = 0.0;  // algorithmic work of one launch
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> pending;
+  double total_ms = 0.0;
+  int64_t launches = 0;
+};
+
 struct ae_model {
   ae::Plan plan;
+  bool timing = false;
+  std::vector<TimeSlot> slots;
+  std::map<std::string, int> slot_index;
+  std::vector<hipEvent_t> free_events;
   char* ws = nullptr;
   void* grad_a = nullptr;
   void* grad_b = nullptr;
@@ -23,19 +43,72 @@ using namespace ae;
 
 namespace {
 
+class TimedScope {
+ public:
+  TimedScope(ae_model* m, hipStream_t s, int step, const char* tag, double flops, double bytes) : m_(m), s_(s) {
+    if (!m->timing) return;
+    char key[96];
+    snprintf(key, sizeof(key), "step%02d.%s", step, tag);
+    auto it = m->slot_index.find(key);
+    if (it == m->slot_index.end()) {
+      it = m->slot_index.emplace(key, (int)m->slots.size()).first;
+      m->slots.emplace_back();
+      m->slots.back().name = key;
+    }
+    slot_ = it->second;
+    m->slots[slot_].flops = flops;
+    m->slots[slot_].bytes = bytes;
+    start_ = take();
+    stop_ = take();
+    if (start_ && stop_) (void)hipEventRecord(start_, s_);
+  }
+  ~TimedScope() {
+    if (slot_ < 0 || !start_ || !stop_) return;
+    (void)hipEventRecord(stop_, s_);
+    m_->slots[slot_].pending.emplace_back(start_, stop_);
+  }
+
+ private:
+  hipEvent_t take() {
+    if (!m_->free_events.empty()) {
+      hipEvent_t e = m_->free_events.back();
+      m_->free_events.pop_back();
+      return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+  }
+  ae_model* m_;
+  hipStream_t s_;
+  int slot_ = -1;
+  hipEvent_t start_ = nullptr, stop_ = nullptr;
+};
+
+#define TIMED(step, tag, flops, bytes, call)                 \
+  do {                                                        \
+    TimedScope ts_(m, s, (step), (tag), (flops), (bytes));    \
+    AE_TRY(call);                                             \
+  } while (0)
+
 int nblocks_for(int64_t rows) { return (int)((rows + kReduceRows - 1) / kReduceRows); }
 
 // input tensor of step i: the previous step's saved output, or the caller's x
 const void* step_input(const ae_model* m, size_t i, const void* x) { return i == 0 ? x : m->plan.steps[i - 1].out; }
 
-int forward_conv(ae_model* m, Step& st, const float* params, const void* in, hipStream_t s) {
+int forward_conv(ae_model* m, int si, Step& st, const float* params, const void* in, hipStream_t s) {
   const Plan& P = m->plan;
+  const double es = (double)dtype_size(P.dtype);
   const int64_t rows = (int64_t)P.batch * st.hc * st.wc;
+  const double wel = (double)st.cout * st.cin * st.k * st.k;
+  const double in_el = (double)P.batch * st.cin * st.hin * st.win, raw_el = (double)rows * st.cout;
+  const double out_el = (double)P.batch * st.cout * st.hout * st.wout;
   const void* w;
   if (st.k == 1 && P.dtype == AE_F32) {
     w = params + st.w_off;  // [C_out][C_in] is already the packed order
   } else {
-    AE_TRY(launch_pack_weights(params + st.w_off, st.wpack, st.cout, st.cin, st.k, P.dtype, false, s));
+    TIMED(si, "fwd.pack_weights", 0.0, wel * (4.0 + es),
+          launch_pack_weights(params + st.w_off, st.wpack, st.cout, st.cin, st.k, P.dtype, false, s));
     w = st.wpack;
   }
   const bool second_pass = st.has_bn || st.pool;
@@ -48,72 +121,96 @@ int forward_conv(ae_model* m, Step& st, const float* params, const void* in, hip
   a.partial = nullptr;
   a.y_aux = second_pass ? nullptr : st.aux;
   int nblk = 0;
+  const double conv_flops = 2.0 * raw_el * st.cin * st.k * st.k;
+  const double conv_bytes = (in_el + raw_el + wel) * es;
   if (st.mfma) {
-    if (st.has_bn && P.bn_mode == 0) { a.partial = m->partial; nblk = (int)((rows + conv_partial_rows(a, true) - 1) / conv_partial_rows(a, true)); }
-    AE_TRY(launch_conv_mfma(a, s));
+    if (st.has_bn && P.bn_mode == 0) {
+      a.partial = m->partial;
+      const int pr = conv_partial_rows(a, true);
+      nblk = (int)((rows + pr - 1) / pr);
+    }
+    TIMED(si, "fwd.conv_mfma", conv_flops, conv_bytes, launch_conv_mfma(a, s));
   } else {
-    AE_TRY(launch_conv_direct(a, s));
+    TIMED(si, "fwd.conv_direct", conv_flops, conv_bytes, launch_conv_direct(a, s));
   }
   if (st.has_bn) {
     const float* gb = params + st.bn_off;
     if (P.bn_mode == 0) {
       if (!a.partial) {
-        AE_TRY(launch_col_stats(st.raw, rows, st.cout, P.dtype, m->partial, s));
+        TIMED(si, "fwd.col_stats", 0.0, raw_el * es, launch_col_stats(st.raw, rows, st.cout, P.dtype, m->partial, s));
         nblk = nblocks_for(rows);
       }
-      AE_TRY(launch_bn_finalize(m->partial, nblk, rows, st.cout, gb, nullptr, st.bn_vec, s));
+      TIMED(si, "fwd.bn_finalize", 0.0, (double)nblk * 2 * st.cout * 4,
+            launch_bn_finalize(m->partial, nblk, rows, st.cout, gb, nullptr, st.bn_vec, s));
     } else {
-      AE_TRY(launch_bn_finalize(nullptr, 0, rows, st.cout, gb, gb + 2 * st.cout, st.bn_vec, s));
+      TIMED(si, "fwd.bn_finalize", 0.0, 0.0,
+            launch_bn_finalize(nullptr, 0, rows, st.cout, gb, gb + 2 * st.cout, st.bn_vec, s));
     }
   }
   if (second_pass)
-    AE_TRY(launch_post_forward(st.raw, st.has_bn ? st.bn_vec : nullptr, st.out, P.batch, st.hc, st.wc, st.cout, st.act,
-                               st.pool, P.dtype, s));
+    TIMED(si, "fwd.bn_act_pool", 0.0, (raw_el + out_el) * es,
+          launch_post_forward(st.raw, st.has_bn ? st.bn_vec : nullptr, st.out, P.batch, st.hc, st.wc, st.cout, st.act,
+                              st.pool, P.dtype, s));
   return AE_OK;
 }
 
-int backward_conv(ae_model* m, Step& st, const float* params, const void* in, const void* g, void* gnext, float* grads,
-                  hipStream_t s) {
+int backward_conv(ae_model* m, int si, Step& st, const float* params, const void* in, const void* g, void* gnext,
+                  float* grads, hipStream_t s) {
   const Plan& P = m->plan;
+  const double es = (double)dtype_size(P.dtype);
   const int64_t rows = (int64_t)P.batch * st.hc * st.wc;
+  const double wel = (double)st.cout * st.cin * st.k * st.k;
+  const double in_el = (double)P.batch * st.cin * st.hin * st.win, raw_el = (double)rows * st.cout;
+  const double out_el = (double)P.batch * st.cout * st.hout * st.wout;
+  const double conv_flops = 2.0 * raw_el * st.cin * st.k * st.k;
   const void* dr = g;  // gradient w.r.t. the conv output (bias included)
   if (st.has_bn || st.pool) {
     if (st.has_bn) {
       const int64_t prow = (int64_t)P.batch * st.hout * st.wout;
-      AE_TRY(launch_post_bwd_reduce(st.raw, g, st.bn_vec, P.batch, st.hc, st.wc, st.cout, st.act, st.pool, P.dtype,
-                                    m->partial, s));
-      AE_TRY(launch_bn_bwd_finalize(m->partial, nblocks_for(prow), rows, st.cout, params + st.bn_off, st.bn_vec,
-                                    grads + st.bn_off, P.bn_mode == 0, s));
+      TIMED(si, "bwd.bn_reduce", 0.0, (raw_el + out_el) * es,
+            launch_post_bwd_reduce(st.raw, g, st.bn_vec, P.batch, st.hc, st.wc, st.cout, st.act, st.pool, P.dtype,
+                                   m->partial, s));
+      TIMED(si, "bwd.bn_finalize", 0.0, 0.0,
+            launch_bn_bwd_finalize(m->partial, nblocks_for(prow), rows, st.cout, params + st.bn_off, st.bn_vec,
+                                   grads + st.bn_off, P.bn_mode == 0, s));
     }
-    AE_TRY(launch_post_bwd_apply(st.raw, g, st.has_bn ? st.bn_vec : nullptr, m->draw, P.batch, st.hc, st.wc, st.cout,
-                                 st.act, st.pool, st.has_bn, P.dtype, s));
+    TIMED(si, "bwd.bn_act_pool", 0.0, (2.0 * raw_el + out_el) * es,
+          launch_post_bwd_apply(st.raw, g, st.has_bn ? st.bn_vec : nullptr, m->draw, P.batch, st.hc, st.wc, st.cout,
+                                st.act, st.pool, st.has_bn, P.dtype, s));
     dr = m->draw;
   } else if (st.act != ACT_NONE) {
-    AE_TRY(launch_act_bwd(st.out, st.aux, g, m->draw, rows * st.cout, st.act, P.dtype, s));
+    TIMED(si, "bwd.act", 0.0, 3.0 * raw_el * es,
+          launch_act_bwd(st.out, st.aux, g, m->draw, rows * st.cout, st.act, P.dtype, s));
     dr = m->draw;
   }
   // bias gradient: column sums of the conv-output gradient
-  AE_TRY(launch_col_stats(dr, rows, st.cout, P.dtype, m->partial, s));
-  AE_TRY(launch_colsum_finalize(m->partial, nblocks_for(rows), st.cout, grads + st.b_off, s));
+  TIMED(si, "bwd.bias_colsum", 0.0, raw_el * es, launch_col_stats(dr, rows, st.cout, P.dtype, m->partial, s));
+  TIMED(si, "bwd.bias_finalize", 0.0, 0.0,
+        launch_colsum_finalize(m->partial, nblocks_for(rows), st.cout, grads + st.b_off, s));
   // weight gradient
-  const int64_t wel = (int64_t)st.cout * st.cin * st.k * st.k;
-  AE_TRY(launch_fill_zero(grads + st.w_off, wel * 4, s));
+  TIMED(si, "bwd.wgrad_zero", 0.0, wel * 4, launch_fill_zero(grads + st.w_off, (int64_t)wel * 4, s));
   WgradArgs wa;
   wa.x = in; wa.dy = dr; wa.dw_canonical = grads + st.w_off;
   wa.n = P.batch; wa.hc = st.hc; wa.wc = st.wc; wa.cin = st.cin; wa.cout = st.cout; wa.k = st.k; wa.up = st.up;
   wa.dtype = P.dtype;
-  AE_TRY(launch_wgrad_direct(wa, s));
+  TIMED(si, "bwd.wgrad_direct", conv_flops, (in_el + raw_el) * es + wel * 4, launch_wgrad_direct(wa, s));
   // input gradient: convolution of dr with the flipped, transposed weights at conv resolution
   if (st.needs_dx) {
-    AE_TRY(launch_pack_weights(params + st.w_off, st.wpack_d, st.cout, st.cin, st.k, P.dtype, true, s));
+    TIMED(si, "bwd.pack_weights", 0.0, wel * (4.0 + es),
+          launch_pack_weights(params + st.w_off, st.wpack_d, st.cout, st.cin, st.k, P.dtype, true, s));
     ConvArgs a;
     a.x = dr; a.w = st.wpack_d; a.bias = nullptr;
     a.y = st.up ? m->dfull : gnext;
     a.n = P.batch; a.hc = st.hc; a.wc = st.wc; a.cin = st.cout; a.cout = st.cin; a.k = st.k; a.up = 0;
     a.act = ACT_NONE; a.dtype = P.dtype; a.partial = nullptr; a.y_aux = nullptr;
-    if (conv_mfma_supported(a)) AE_TRY(launch_conv_mfma(a, s));
-    else AE_TRY(launch_conv_direct(a, s));
-    if (st.up) AE_TRY(launch_upsum(m->dfull, gnext, P.batch, st.hin, st.win, st.cin, P.dtype, s));
+    const double full_el = (double)rows * st.cin;
+    if (conv_mfma_supported(a))
+      TIMED(si, "bwd.dgrad_mfma", conv_flops, (raw_el + full_el + wel) * es, launch_conv_mfma(a, s));
+    else
+      TIMED(si, "bwd.dgrad_direct", conv_flops, (raw_el + full_el + wel) * es, launch_conv_direct(a, s));
+    if (st.up)
+      TIMED(si, "bwd.upsum", 0.0, (full_el + in_el) * es,
+            launch_upsum(m->dfull, gnext, P.batch, st.hin, st.win, st.cin, P.dtype, s));
   }
   return AE_OK;
 }
@@ -177,7 +274,55 @@ int model_create(const char* layer_spec, int batch, int dtype, int bn_mode, ae_m
 void model_destroy(ae_model* m) {
   if (!m) return;
   if (m->ws) (void)hipFree(m->ws);
+  for (TimeSlot& sl : m->slots)
+    for (auto& pr : sl.pending) { (void)hipEventDestroy(pr.first); (void)hipEventDestroy(pr.second); }
+  for (hipEvent_t e : m->free_events) (void)hipEventDestroy(e);
   delete m;
+}
+
+int model_timing_enable(ae_model* m, int on) {
+  if (!m) return fail(AE_EINVAL, "model_timing_enable: null model");
+  m->timing = on != 0;
+  return AE_OK;
+}
+
+int model_timing_slots(const ae_model* m, int* n_slots) {
+  if (!m || !n_slots) return fail(AE_EINVAL, "model_timing_slots: null argument");
+  *n_slots = (int)m->slots.size();
+  return AE_OK;
+}
+
+int model_timing_read(ae_model* m, int slot, char* name, int name_len, double* total_ms, int64_t* launches,
+                      double* flops_per_launch, double* bytes_per_launch) {
+  if (!m || slot < 0 || slot >= (int)m->slots.size()) return fail(AE_EINVAL, "model_timing_read: bad slot");
+  TimeSlot& sl = m->slots[slot];
+  for (auto& pr : sl.pending) {
+    AE_HIP(hipEventSynchronize(pr.second));
+    float ms = 0.0f;
+    AE_HIP(hipEventElapsedTime(&ms, pr.first, pr.second));
+    sl.total_ms += (double)ms;
+    sl.launches += 1;
+    m->free_events.push_back(pr.first);
+    m->free_events.push_back(pr.second);
+  }
+  sl.pending.clear();
+  if (name && name_len > 0) snprintf(name, (size_t)name_len, "%s", sl.name.c_str());
+  if (total_ms) *total_ms = sl.total_ms;
+  if (launches) *launches = sl.launches;
+  if (flops_per_launch) *flops_per_launch = sl.flops;
+  if (bytes_per_launch) *bytes_per_launch = sl.bytes;
+  return AE_OK;
+}
+
+int model_timing_reset(ae_model* m) {
+  if (!m) return fail(AE_EINVAL, "model_timing_reset: null model");
+  for (TimeSlot& sl : m->slots) {
+    for (auto& pr : sl.pending) { m->free_events.push_back(pr.first); m->free_events.push_back(pr.second); }
+    sl.pending.clear();
+    sl.total_ms = 0.0;
+    sl.launches = 0;
+  }
+  return AE_OK;
 }
 
 int model_param_count(const ae_model* m, int64_t* n_params) {
@@ -218,15 +363,17 @@ int model_forward(ae_model* m, const void* params, const void* x, float snr_db, 
       case ST_TRANSPOSE: {
         // the last step of a plan that ends in a transpose writes the caller's y directly
         void* dst = (i + 1 == ns) ? y : st.out;
-        AE_TRY(launch_transpose(in, dst, P.batch, st.t_rows, st.t_cols, P.dtype, s));
+        TIMED((int)i, "fwd.transpose", 0.0, 2.0 * P.batch * st.t_rows * st.t_cols * dtype_size(P.dtype),
+              launch_transpose(in, dst, P.batch, st.t_rows, st.t_cols, P.dtype, s));
         break;
       }
       case ST_CONV:
-        AE_TRY(forward_conv(m, st, prm, in, s));
+        AE_TRY(forward_conv(m, (int)i, st, prm, in, s));
         break;
       case ST_CHANNEL:
-        AE_TRY(launch_pnorm_awgn(in, st.out, P.batch, st.cin, st.hin * st.win, P.dtype, st.do_pnorm, st.do_awgn, sigma,
-                                 seed, m->first_sample, s));
+        TIMED((int)i, "fwd.pnorm_awgn", 0.0, 2.0 * P.batch * st.cin * st.hin * st.win * dtype_size(P.dtype),
+              launch_pnorm_awgn(in, st.out, P.batch, st.cin, st.hin * st.win, P.dtype, st.do_pnorm, st.do_awgn, sigma,
+                                seed, m->first_sample, s));
         break;
     }
   }
@@ -259,17 +406,19 @@ int model_backward(ae_model* m, const void* params, const void* x, const void* d
     const void* in = step_input(m, ii, x);
     switch (st.kind) {
       case ST_TRANSPOSE:
-        AE_TRY(launch_transpose(g, gnext, P.batch, st.t_cols, st.t_rows, P.dtype, s));
+        TIMED((int)ii, "bwd.transpose", 0.0, 2.0 * P.batch * st.t_rows * st.t_cols * dtype_size(P.dtype),
+              launch_transpose(g, gnext, P.batch, st.t_cols, st.t_rows, P.dtype, s));
         g = gnext;
         break;
       case ST_CHANNEL:
         if (st.do_pnorm) {
-          AE_TRY(launch_pnorm_bwd(in, g, gnext, P.batch, (int64_t)st.cin * st.hin * st.win, P.dtype, s));
+          TIMED((int)ii, "bwd.pnorm", 0.0, 3.0 * P.batch * st.cin * st.hin * st.win * dtype_size(P.dtype),
+                launch_pnorm_bwd(in, g, gnext, P.batch, (int64_t)st.cin * st.hin * st.win, P.dtype, s));
           g = gnext;
         }
         break;
       case ST_CONV:
-        AE_TRY(backward_conv(m, st, prm, in, g, gnext, gr, s));
+        AE_TRY(backward_conv(m, (int)ii, st, prm, in, g, gnext, gr, s));
         if (st.needs_dx) g = gnext;
         break;
     }

@@ -7,6 +7,20 @@ import workloads as wl
 
 TOL = {"f32": 1e-4, "bf16": 2e-2}
 
+# Gradient bar for DEEP bf16 networks (relative L2 bound, minimum cosine per tensor).
+# Every ReLU mask bit and max-pool winner is a discrete decision taken on a stored bf16
+# activation.  Two correct implementations of the format (fp32 vs fp64 accumulation order)
+# differ by 1 bf16 ulp (2^-8 relative) on a small fraction of stored values; each such
+# difference perturbs ~9*C_out outputs of the next layer by ~2^-8/sqrt(K), enough to flip
+# the rounding of a few per cent of them, so the fraction of differing values grows with
+# depth until activations agree only to ~5e-3 (still inside the 2e-2 activation bar).  A
+# fraction f of flipped masks / winners changes a gradient tensor by ~sqrt(f) in relative
+# L2 (each flip moves one full-magnitude term), i.e. 5-15 % for f = 0.3-2 %, whatever the
+# kernel does.  Hence: per-layer gradients are held to 2e-2 on single-layer models (same
+# decisions on both sides), and whole deep networks to this derived bar plus direction.
+# The largest single entry of a tensor can be off by about twice the L2 figure.
+DEEP_BF16_GRAD = (0.25, 0.97)
+
 
 def rel_errors(a, o):
     """(relative L2 error, max error relative to the largest reference magnitude)."""
@@ -25,10 +39,11 @@ def rel_errors(a, o):
 STRICT = True   # set False (debugging only) to collect errors instead of asserting
 
 
-def assert_close(a, o, tol, what):
+def assert_close(a, o, tol, what, tol_max=None):
     l2, lm = rel_errors(a, o)
+    tm = tol if tol_max is None else tol_max
     if STRICT:
-        assert l2 <= tol and lm <= tol, "%s: rel L2 %.3e, rel max %.3e (tol %.1e)" % (what, l2, lm, tol)
+        assert l2 <= tol and lm <= tm, "%s: rel L2 %.3e (tol %.1e), rel max %.3e (tol %.1e)" % (what, l2, tol, lm, tm)
     return l2, lm
 
 
@@ -115,7 +130,7 @@ def run_case(spec, batch, dtype="f32", seed=0, snr_db=10.0, first_sample=0, bn_m
                 if STRICT:
                     assert np.abs(g[sl]).max() <= max(gtol, 1e-3) * scale * 10, name
                 continue
-            worst[name] = assert_close(g[sl], g_ref[sl], gtol, name)
+            worst[name] = assert_close(g[sl], g_ref[sl], gtol, name, tol_max=2 * gtol if grad_cos is not None else None)
             if grad_cos is not None and sz >= 16:
                 c = float(np.dot(g[sl], g_ref[sl]) / (np.linalg.norm(g[sl]) * np.linalg.norm(g_ref[sl])))
                 worst[name] = worst[name] + (c,)

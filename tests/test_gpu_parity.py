@@ -6,7 +6,7 @@ import pytest
 
 import oracle.ae_oracle as orc
 import workloads as wl
-from parity_util import TOL, assert_close, rel_errors, run_case, to_dev
+from parity_util import DEEP_BF16_GRAD, TOL, assert_close, rel_errors, run_case, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -101,7 +101,11 @@ SMALL = [
 @pytest.mark.parametrize("case", range(len(SMALL)))
 def test_small_networks_forward_backward(ae, case, dtype):
     spec, batch = SMALL[case]
-    run_case(spec, batch, dtype=dtype, seed=100 + case, snr_db=7.0, first_sample=3)
+    # bf16: a 4-element bias gradient upstream of a batch-stat BN is a sum that cancels almost
+    # completely (the BN input gradient sums to zero per channel), so its relative error is a
+    # few times the bf16 rounding of its terms
+    run_case(spec, batch, dtype=dtype, seed=100 + case, snr_db=7.0, first_sample=3,
+             grad_tol=5e-2 if dtype == "bf16" else None)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -171,7 +175,7 @@ def test_cfg2_reduced_resolution(ae, snr_db):
 
 def test_cfg3_reduced_resolution_bf16(ae):
     spec = wl.scaled_spec("cfg3", 16)
-    run_case(spec, 6, dtype="bf16", seed=2, snr_db=5.0)
+    run_case(spec, 6, dtype="bf16", seed=2, snr_db=5.0, grad_tol=DEEP_BF16_GRAD[0], grad_cos=DEEP_BF16_GRAD[1])
 
 
 def test_cfg4_launch_and_error_counts(ae):
@@ -210,7 +214,26 @@ def test_cfg4_launch_and_error_counts(ae):
 
 def test_cfg5_reduced_resolution_bf16(ae):
     spec = wl.scaled_spec("cfg5", 32)
-    run_case(spec, 4, dtype="bf16", seed=4, snr_db=10.0)
+    run_case(spec, 4, dtype="bf16", seed=4, snr_db=10.0, grad_tol=DEEP_BF16_GRAD[0], grad_cos=DEEP_BF16_GRAD[1])
+
+
+# ------------------------------------------------------------------ single layers in bf16: gradients at 2e-2
+LAYERS_BF16 = [
+    ("in:64x16x16,conv3:128,bn,relu,pool2", 4),
+    ("in:128x8x8,up2,conv3:64,relu", 4),
+    ("in:64x8x8,conv3:64", 3),
+    ("in:256x1x1,fc:512,relu", 64),
+    ("in:128x4x4,conv1:64,pnorm,awgn", 8),
+    ("in:64x4x4,conv1:128,sigmoid", 8),
+    ("in:3x16x16,conv3:64,bn,relu,pool2", 4),
+    ("in:64x8x8,up2,conv3:3,sigmoid", 4),
+]
+
+
+@pytest.mark.parametrize("case", range(len(LAYERS_BF16)))
+def test_single_layers_bf16_gradients(ae, case):
+    spec, batch = LAYERS_BF16[case]
+    run_case(spec, batch, dtype="bf16", seed=300 + case, snr_db=10.0)
 
 
 # ------------------------------------------------------------------ error handling (host side, no kernel faults)
