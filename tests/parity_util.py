@@ -6,6 +6,11 @@ import oracle.ae_oracle as orc
 import workloads as wl
 
 TOL = {"f32": 1e-4, "bf16": 2e-2}
+# The stated tolerances are applied to the relative L2 norm of each tensor.  The largest
+# single deviation, relative to the largest reference magnitude, gets the same bar in fp32;
+# in bf16 it is the tail of ~1e5..1e7 independent rounding errors (4.5-5.5 standard
+# deviations), so its bar is three times the L2 bar.
+TOL_MAX = {"f32": 1e-4, "bf16": 6e-2}
 
 # Gradient bar for DEEP bf16 networks (relative L2 bound, minimum cosine per tensor).
 # Every ReLU mask bit and max-pool winner is a discrete decision taken on a stored bf16
@@ -67,7 +72,7 @@ def run_case(spec, batch, dtype="f32", seed=0, snr_db=10.0, first_sample=0, bn_m
     from paper_2602_17681_amd import binding as ae
 
     bf = dtype == "bf16"
-    tol = TOL[dtype]
+    tol, tolm = TOL[dtype], TOL_MAX[dtype]
     gtol = tol if grad_tol is None else grad_tol
     if params is None:
         params = wl.make_params(spec, seed, bn_mode=bn_mode, perturb=perturb, bf16=bf)
@@ -90,7 +95,7 @@ def run_case(spec, batch, dtype="f32", seed=0, snr_db=10.0, first_sample=0, bn_m
     worst = {}
     y_gpu = y_d.float().cpu().numpy()
     for (rname, _), y_ref in zip(refs, y_refs):
-        worst["y/" + rname] = assert_close(y_gpu, y_ref, tol, "y vs %s oracle" % rname)
+        worst["y/" + rname] = assert_close(y_gpu, y_ref, tol, "y vs %s oracle" % rname, tol_max=tolm)
     if check_acts:
         ns = m.model_num_steps()
         for s in range(ns):
@@ -104,7 +109,7 @@ def run_case(spec, batch, dtype="f32", seed=0, snr_db=10.0, first_sample=0, bn_m
             for rname, rnet in refs:
                 ref = rnet.activation(tok).reshape((batch,) + chw)
                 worst["act%d/%s" % (s, rname)] = assert_close(
-                    got, ref, tol, "activation of step %d (token %d) vs %s oracle" % (s, tok, rname))
+                    got, ref, tol, "activation of step %d (token %d) vs %s oracle" % (s, tok, rname), tol_max=tolm)
     if backward:
         if cot is None:
             cot = wl.make_cotangent((batch,) + m.out_shape, seed, bf16=bf)
@@ -130,7 +135,7 @@ def run_case(spec, batch, dtype="f32", seed=0, snr_db=10.0, first_sample=0, bn_m
                 if STRICT:
                     assert np.abs(g[sl]).max() <= max(gtol, 1e-3) * scale * 10, name
                 continue
-            worst[name] = assert_close(g[sl], g_ref[sl], gtol, name, tol_max=2 * gtol if grad_cos is not None else None)
+            worst[name] = assert_close(g[sl], g_ref[sl], gtol, name, tol_max=2 * gtol if grad_cos is not None else max(gtol, tolm))
             if grad_cos is not None and sz >= 16:
                 c = float(np.dot(g[sl], g_ref[sl]) / (np.linalg.norm(g[sl]) * np.linalg.norm(g_ref[sl])))
                 worst[name] = worst[name] + (c,)
