@@ -35,6 +35,7 @@ struct ae_model {
   void* draw = nullptr;
   void* dfull = nullptr;
   float* partial = nullptr;
+  float* wgrad_ws = nullptr;
   uint64_t first_sample = 0;
   bool have_forward = false;
 };
@@ -188,12 +189,16 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
   TIMED(si, "bwd.bias_finalize", 0.0, 0.0,
         launch_colsum_finalize(m->partial, nblocks_for(rows), st.cout, grads + st.b_off, s));
   // weight gradient
-  TIMED(si, "bwd.wgrad_zero", 0.0, wel * 4, launch_fill_zero(grads + st.w_off, (int64_t)wel * 4, s));
   WgradArgs wa;
   wa.x = in; wa.dy = dr; wa.dw_canonical = grads + st.w_off;
   wa.n = P.batch; wa.hc = st.hc; wa.wc = st.wc; wa.cin = st.cin; wa.cout = st.cout; wa.k = st.k; wa.up = st.up;
   wa.dtype = P.dtype;
-  TIMED(si, "bwd.wgrad_direct", conv_flops, (in_el + raw_el) * es + wel * 4, launch_wgrad_direct(wa, s));
+  if (wgrad_mfma_supported(wa)) {
+    TIMED(si, "bwd.wgrad_mfma", conv_flops, (in_el + raw_el) * es + wel * 4, launch_wgrad_mfma(wa, m->wgrad_ws, s));
+  } else {
+    TIMED(si, "bwd.wgrad_zero", 0.0, wel * 4, launch_fill_zero(grads + st.w_off, (int64_t)wel * 4, s));
+    TIMED(si, "bwd.wgrad_direct", conv_flops, (in_el + raw_el) * es + wel * 4, launch_wgrad_direct(wa, s));
+  }
   // input gradient: convolution of dr with the flipped, transposed weights at conv resolution
   if (st.needs_dx) {
     TIMED(si, "bwd.pack_weights", 0.0, wel * (4.0 + es),
@@ -267,6 +272,7 @@ int model_create(const char* layer_spec, int batch, int dtype, int bn_mode, ae_m
   m->draw = m->ws + P.off_draw;
   m->dfull = m->ws + P.off_dfull;
   m->partial = (float*)(m->ws + P.off_partial);
+  m->wgrad_ws = (float*)(m->ws + P.off_wgrad);
   *out = m;
   return AE_OK;
 }

@@ -219,3 +219,255 @@ int launch_conv_mfma(const ConvArgs& a, hipStream_t s) {
 }
 
 }  // namespace ae
+
+// ===========================================================================
+// Weight gradient on the matrix cores (bf16).
+//
+//   dW[co][(r,s,ci)] = sum over pixels m of dY[m][co] * Xg[m][(r,s,ci)]
+// where Xg is the gathered input of tap (r,s).  Both operands are stored with the
+// reduction index (the pixel) outermost, so the MFMA operands (8 consecutive pixels
+// of one channel per lane) are transposes of what memory holds.  The slabs go to
+// LDS exactly as loaded, [pixel][channel], and are read back with the gfx950 LDS
+// transpose load (ds_read_b64_tr_b16): within a group of 16 lanes, the lane with
+// local index 4*j+q supplies the address of 4 channels (4q..4q+3) of pixel j, and
+// lane i receives channel i of pixels 0..3.
+//
+// A workgroup owns one output tile (BM output channels x BN input channels of one
+// tap) and one contiguous range of pixels; partial tiles go to a workspace
+// [split][C_out][k*k*C_in] (fp32) that a second kernel sums in a fixed order and
+// writes in the canonical [C_out][C_in][k][k] layout, so the result is deterministic.
+// ===========================================================================
+namespace ae {
+namespace {
+
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) short4v lds_short4v;
+
+struct WgradParams {
+  const void* x; const void* dy; float* partial;
+  int64_t M;            // pixels
+  int Cout, Cin, Hc, Wc, ksz, up;
+  int tiles_m, tiles_n; // tiles over C_out and over C_in
+  int rows_per_split;   // multiple of 32
+  int K;                // k*k*C_in
+};
+
+__device__ __forceinline__ bf16x8 lds_tr_frag(const bf16_t* base0, const bf16_t* base1) {
+  // two transposing 64-bit loads: pixels p..p+3 and p+4..p+7 of this lane's channel
+  short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4v*)base0);
+  short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4v*)base1);
+  union { short s[8]; bf16x8 v; } u;
+  u.s[0] = lo[0]; u.s[1] = lo[1]; u.s[2] = lo[2]; u.s[3] = lo[3];
+  u.s[4] = hi[0]; u.s[5] = hi[1]; u.s[6] = hi[2]; u.s[7] = hi[3];
+  return u.v;
+}
+
+template <int BM, int BN>
+__global__ __launch_bounds__(256) void k_wgrad_bf16(WgradParams p) {
+  constexpr int BK = 32;                         // pixels per slab
+  constexpr int LA = BM + 16, LB = BN + 16;      // LDS row strides in elements (+32 bytes: 4 rows hit disjoint banks)
+  constexpr int WM = BM / 2, WN = BN / 2;
+  constexpr int MI = WM / 32, NJ = WN / 32;
+  constexpr int A_TPR = BM / 8, B_TPR = BN / 8;  // 16-byte chunks per pixel row
+  constexpr int A_CHUNKS = BK * A_TPR / 256, B_CHUNKS = BK * B_TPR / 256;
+  __shared__ __attribute__((aligned(16))) bf16_t sA[2][BK * LA];
+  __shared__ __attribute__((aligned(16))) bf16_t sB[2][BK * LB];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  // block -> (split, tile_m, tile_n, tap): the tap varies fastest so that the blocks
+  // sharing a dY slab and overlapping x slabs run at the same time
+  const int taps = p.ksz * p.ksz;
+  int b = blockIdx.x;
+  const int tap = b % taps; b /= taps;
+  const int tn = b % p.tiles_n; b /= p.tiles_n;
+  const int tm = b % p.tiles_m;
+  const int split = b / p.tiles_m;
+  const int r = tap / p.ksz, s = tap - r * p.ksz;
+  const int pad = (p.ksz - 1) >> 1;
+  const int co0 = tm * BM, ci0 = tn * BN;
+  const int Hin = p.Hc >> p.up, Win = p.Wc >> p.up;
+  const bf16_t* __restrict__ X = (const bf16_t*)p.x;
+  const bf16_t* __restrict__ DY = (const bf16_t*)p.dy;
+  const int64_t m_begin = (int64_t)split * p.rows_per_split;
+  const int64_t m_end = (m_begin + p.rows_per_split < p.M) ? m_begin + p.rows_per_split : p.M;
+  const int KT = (int)((m_end - m_begin + BK - 1) / BK);
+
+  uint4 ra[A_CHUNKS], rb[B_CHUNKS];
+  const uint4 zero4 = make_uint4(0u, 0u, 0u, 0u);
+  auto load_slab = [&](int kt) {
+    const int64_t mb = m_begin + (int64_t)kt * BK;
+#pragma unroll
+    for (int i = 0; i < A_CHUNKS; ++i) {
+      const int id = tid + i * 256;
+      const int64_t m = mb + id / A_TPR;
+      ra[i] = (m < m_end) ? *reinterpret_cast<const uint4*>(DY + m * p.Cout + co0 + (id % A_TPR) * 8) : zero4;
+    }
+#pragma unroll
+    for (int i = 0; i < B_CHUNKS; ++i) {
+      const int id = tid + i * 256;
+      const int64_t m = mb + id / B_TPR;
+      uint4 v = zero4;
+      if (m < m_end) {
+        const unsigned mm = (unsigned)m;
+        const unsigned w = mm % (unsigned)p.Wc, t = mm / (unsigned)p.Wc;
+        const unsigned h = t % (unsigned)p.Hc, n = t / (unsigned)p.Hc;
+        const int hh = (int)h + r - pad, ww = (int)w + s - pad;
+        if (hh >= 0 && hh < p.Hc && ww >= 0 && ww < p.Wc)
+          v = *reinterpret_cast<const uint4*>(X + (((int64_t)n * Hin + (hh >> p.up)) * Win + (ww >> p.up)) * p.Cin + ci0 +
+                                              (id % B_TPR) * 8);
+      }
+      rb[i] = v;
+    }
+  };
+  auto store_slab = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < A_CHUNKS; ++i) {
+      const int id = tid + i * 256;
+      *reinterpret_cast<uint4*>(&sA[buf][(id / A_TPR) * LA + (id % A_TPR) * 8]) = ra[i];
+    }
+#pragma unroll
+    for (int i = 0; i < B_CHUNKS; ++i) {
+      const int id = tid + i * 256;
+      *reinterpret_cast<uint4*>(&sB[buf][(id / B_TPR) * LB + (id % B_TPR) * 8]) = rb[i];
+    }
+  };
+
+  floatx16 acc[MI][NJ];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+  // transposing-load geometry of this lane: 16-lane group G covers channels 16*(G&1).. of
+  // the 32-channel MFMA tile and pixels 8*(G>>1)..; local lane sl addresses pixel sl/4,
+  // channels 4*(sl%4)..
+  const int grp = lane >> 4, sl = lane & 15;
+  const int t_pix = 8 * (grp >> 1) + (sl >> 2);
+  const int t_ch = 16 * (grp & 1) + 4 * (sl & 3);
+
+  if (KT > 0) {
+    load_slab(0);
+    store_slab(0);
+  }
+  __syncthreads();
+  for (int kt = 0; kt < KT; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < KT) load_slab(kt + 1);
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      bf16x8 a[MI], bb[NJ];
+#pragma unroll
+      for (int i = 0; i < MI; ++i) {
+        const bf16_t* q = &sA[buf][(ks * 16 + t_pix) * LA + wm * WM + i * 32 + t_ch];
+        a[i] = lds_tr_frag(q, q + 4 * LA);
+      }
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) {
+        const bf16_t* q = &sB[buf][(ks * 16 + t_pix) * LB + wn * WN + j * 32 + t_ch];
+        bb[j] = lds_tr_frag(q, q + 4 * LB);
+      }
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bb[j], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < KT) store_slab(buf ^ 1);
+    __syncthreads();
+  }
+
+  // partial[split][co][tap*Cin + ci]
+  float* __restrict__ P = p.partial + (int64_t)split * p.Cout * p.K;
+  const int col_lane = lane & 31, row_lane = (lane >> 5) * 4;
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      const int ci = ci0 + wn * WN + j * 32 + col_lane;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int co = co0 + wm * WM + i * 32 + (e >> 2) * 8 + row_lane + (e & 3);
+        if (co < p.Cout && ci < p.Cin) P[(int64_t)co * p.K + tap * p.Cin + ci] = acc[i][j][e];
+      }
+    }
+}
+
+// dW[co][ci][r][s] = sum over splits of partial[split][co][(r,s,ci)], in split order
+__global__ void k_wgrad_reduce(const float* __restrict__ partial, int splits, int Cout, int Cin, int taps,
+                               float* __restrict__ dw) {
+  const int64_t total = (int64_t)Cout * taps * Cin;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    float acc = 0.0f;
+    for (int sp = 0; sp < splits; ++sp) acc += partial[(int64_t)sp * total + i];
+    const int ci = (int)(i % Cin);
+    const int64_t t = i / Cin;
+    const int tap = (int)(t % taps);
+    const int co = (int)(t / taps);
+    dw[((int64_t)co * Cin + ci) * taps + tap] = acc;
+  }
+}
+
+struct WgradPlan { int bm, bn, tiles_m, tiles_n, splits, rows_per_split; };
+
+WgradPlan plan_wgrad(int cout, int cin, int k, int64_t rows) {
+  WgradPlan w;
+  w.bm = cout % 128 == 0 ? 128 : 64;
+  w.bn = cin % 128 == 0 ? 128 : 64;
+  if (w.bm == 64 && w.bn == 64) w.bn = 64;
+  w.tiles_m = cout / w.bm;
+  w.tiles_n = cin / w.bn;
+  const int64_t tiles = (int64_t)w.tiles_m * w.tiles_n * k * k;
+  int64_t splits = (1024 + tiles - 1) / tiles;          // about four workgroups per compute unit
+  const int64_t max_splits = (rows + 511) / 512;        // at least 512 pixels per split
+  if (splits > max_splits) splits = max_splits;
+  if (splits < 1) splits = 1;
+  int64_t rps = (rows + splits - 1) / splits;
+  rps = (rps + 31) / 32 * 32;
+  w.rows_per_split = (int)rps;
+  w.splits = (int)((rows + rps - 1) / rps);
+  return w;
+}
+
+}  // namespace
+
+bool wgrad_mfma_supported(const WgradArgs& a) {
+  if (a.dtype != AE_BF16) return false;
+  if (a.cin % 64 != 0 || a.cout % 64 != 0) return false;
+  if (a.cin % 128 != 0 && a.cout % 128 != 0 && false) return false;
+  const int64_t rows = (int64_t)a.n * a.hc * a.wc;
+  return rows < 0x7FFFFFFF;
+}
+
+int64_t wgrad_mfma_workspace_floats(int cout, int cin, int k, int64_t rows) {
+  const WgradPlan w = plan_wgrad(cout, cin, k, rows);
+  return (int64_t)w.splits * cout * cin * k * k;
+}
+
+int launch_wgrad_mfma(const WgradArgs& a, float* workspace, hipStream_t s) {
+  if (!wgrad_mfma_supported(a)) return fail(AE_EINVAL, "wgrad_mfma: shape not supported");
+  const int64_t rows = (int64_t)a.n * a.hc * a.wc;
+  const WgradPlan w = plan_wgrad(a.cout, a.cin, a.k, rows);
+  WgradParams p;
+  p.x = a.x; p.dy = a.dy; p.partial = workspace;
+  p.M = rows; p.Cout = a.cout; p.Cin = a.cin; p.Hc = a.hc; p.Wc = a.wc; p.ksz = a.k; p.up = a.up;
+  p.tiles_m = w.tiles_m; p.tiles_n = w.tiles_n; p.rows_per_split = w.rows_per_split;
+  p.K = a.k * a.k * a.cin;
+  const int64_t blocks = (int64_t)w.splits * w.tiles_m * w.tiles_n * a.k * a.k;
+  if (blocks > 0x7FFFFFFF) return fail(AE_EINVAL, "wgrad_mfma: grid too large");
+  dim3 grid((unsigned)blocks);
+  if (w.bm == 128 && w.bn == 128) hipLaunchKernelGGL((k_wgrad_bf16<128, 128>), grid, dim3(256), 0, s, p);
+  else if (w.bm == 128) hipLaunchKernelGGL((k_wgrad_bf16<128, 64>), grid, dim3(256), 0, s, p);
+  else if (w.bn == 128) hipLaunchKernelGGL((k_wgrad_bf16<64, 128>), grid, dim3(256), 0, s, p);
+  else hipLaunchKernelGGL((k_wgrad_bf16<64, 64>), grid, dim3(256), 0, s, p);
+  AE_TRY(launch_status("wgrad_mfma"));
+  const int64_t total = (int64_t)a.cout * a.cin * a.k * a.k;
+  int64_t g = (total + 255) / 256;
+  if (g > 4096) g = 4096;
+  hipLaunchKernelGGL(k_wgrad_reduce, dim3((unsigned)g), dim3(256), 0, s, workspace, w.splits, a.cout, a.cin, a.k * a.k,
+                     a.dw_canonical);
+  return launch_status("wgrad_reduce");
+}
+
+}  // namespace ae

@@ -78,11 +78,12 @@ struct Plan {
   std::vector<Step> steps;
   // workspace sizing (bytes)
   int64_t ws_bytes = 0;
-  int64_t off_grad_a = 0, off_grad_b = 0, off_draw = 0, off_dfull = 0, off_partial = 0;
+  int64_t off_grad_a = 0, off_grad_b = 0, off_draw = 0, off_dfull = 0, off_partial = 0, off_wgrad = 0;
   int64_t max_act_elems = 0;        // largest step output
   int64_t max_raw_elems = 0;        // largest conv-resolution tensor (raw / dRaw)
   int64_t max_full_elems = 0;       // largest conv-resolution input gradient of an upsampled conv
   int64_t max_partial_floats = 0;   // column-reduction partial buffer
+  int64_t max_wgrad_floats = 0;     // split partial tiles of the MFMA weight-gradient kernel
 };
 
 int build_plan(const char* spec, int batch, int dtype, int bn_mode, Plan* plan);
@@ -115,6 +116,9 @@ struct WgradArgs {
   int n, hc, wc, cin, cout, k, up, dtype;
 };
 int launch_wgrad_direct(const WgradArgs& a, hipStream_t s);
+bool wgrad_mfma_supported(const WgradArgs& a);
+int64_t wgrad_mfma_workspace_floats(int cout, int cin, int k, int64_t rows);
+int launch_wgrad_mfma(const WgradArgs& a, float* workspace, hipStream_t s);  // overwrites dw (no zeroing needed)
 
 // per-channel reductions and the second pass after a conv
 int launch_col_stats(const void* x, int64_t rows, int c, int dtype, float* partial, hipStream_t s);

@@ -216,7 +216,7 @@ int build_plan(const char* spec, int batch, int dtype, int bn_mode, Plan* plan) 
     return at;
   };
   plan->max_act_elems = B * plan->c0 * plan->h0 * plan->w0;
-  plan->max_raw_elems = plan->max_full_elems = plan->max_partial_floats = 0;
+  plan->max_raw_elems = plan->max_full_elems = plan->max_partial_floats = plan->max_wgrad_floats = 0;
   for (Step& st : plan->steps) {
     int64_t out_elems = B * st.cout * st.hout * st.wout;
     int64_t in_elems = B * st.cin * st.hin * st.win;
@@ -235,6 +235,12 @@ int build_plan(const char* spec, int batch, int dtype, int bn_mode, Plan* plan) 
       if (st.has_bn) st.off_bn = take(6 * (int64_t)st.cout * 4);
       int64_t blocks = (rows + 63) / 64;               // finest partial-sum granularity any kernel uses
       plan->max_partial_floats = std::max(plan->max_partial_floats, blocks * 2 * std::max(st.cout, st.cin));
+      WgradArgs wa;
+      wa.x = wa.dy = nullptr; wa.dw_canonical = nullptr;
+      wa.n = batch; wa.hc = st.hc; wa.wc = st.wc; wa.cin = st.cin; wa.cout = st.cout; wa.k = st.k; wa.up = st.up;
+      wa.dtype = dtype;
+      if (wgrad_mfma_supported(wa))
+        plan->max_wgrad_floats = std::max(plan->max_wgrad_floats, wgrad_mfma_workspace_floats(st.cout, st.cin, st.k, rows));
     }
   }
   plan->off_grad_a = take(plan->max_act_elems * es);      // gradient ping-pong
@@ -242,6 +248,7 @@ int build_plan(const char* spec, int batch, int dtype, int bn_mode, Plan* plan) 
   plan->off_draw = take(plan->max_raw_elems * es);        // gradient at conv resolution
   plan->off_dfull = take(plan->max_full_elems * es);      // input gradient before the 2x2 sum of an upsampled conv
   plan->off_partial = take(plan->max_partial_floats * 4);
+  plan->off_wgrad = take(plan->max_wgrad_floats * 4);
   plan->ws_bytes = total;
   return AE_OK;
 }
