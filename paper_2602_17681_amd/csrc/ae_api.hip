@@ -92,7 +92,7 @@ class TimedScope {
     AE_TRY(call);                                             \
   } while (0)
 
-int nblocks_for(int64_t rows) { return (int)((rows + kReduceRows - 1) / kReduceRows); }
+int nblocks_for(int64_t rows) { return reduce_blocks(rows); }
 
 // input tensor of step i: the previous step's saved output, or the caller's x
 const void* step_input(const ae_model* m, size_t i, const void* x) { return i == 0 ? x : m->plan.steps[i - 1].out; }
@@ -104,8 +104,16 @@ int forward_conv(ae_model* m, int si, Step& st, const float* params, const void*
   const double wel = (double)st.cout * st.cin * st.k * st.k;
   const double in_el = (double)P.batch * st.cin * st.hin * st.win, raw_el = (double)rows * st.cout;
   const double out_el = (double)P.batch * st.cout * st.hout * st.wout;
-  const void* w;
-  if (st.k == 1 && P.dtype == AE_F32) {
+  if (st.thin == 2) {
+    TIMED(si, "fwd.conv_thin_out", 2.0 * raw_el * st.cin * st.k * st.k, (in_el + raw_el) * es,
+          launch_thin_out_conv(in, params + st.w_off, params + st.b_off, st.out, st.aux, P.batch, st.hc, st.wc, st.cout,
+                               st.cin, st.up, st.act, P.dtype, s));
+    return AE_OK;
+  }
+  const void* w = nullptr;
+  if (st.thin == 1) {
+    // canonical weights are read directly
+  } else if (st.k == 1 && P.dtype == AE_F32) {
     w = params + st.w_off;  // [C_out][C_in] is already the packed order
   } else {
     TIMED(si, "fwd.pack_weights", 0.0, wel * (4.0 + es),
@@ -124,7 +132,15 @@ int forward_conv(ae_model* m, int si, Step& st, const float* params, const void*
   int nblk = 0;
   const double conv_flops = 2.0 * raw_el * st.cin * st.k * st.k;
   const double conv_bytes = (in_el + raw_el + wel) * es;
-  if (st.mfma) {
+  if (st.thin == 1) {
+    if (st.has_bn && P.bn_mode == 0) {
+      a.partial = m->partial;
+      nblk = (int)((rows + thin_in_partial_rows() - 1) / thin_in_partial_rows());
+    }
+    TIMED(si, "fwd.conv_thin_in", conv_flops, conv_bytes,
+          launch_thin_in_conv(in, params + st.w_off, a.bias, a.y, a.partial, P.batch, st.hc, st.wc, st.cin, st.cout, 0,
+                              a.act, P.dtype, s));
+  } else if (st.mfma) {
     if (st.has_bn && P.bn_mode == 0) {
       a.partial = m->partial;
       const int pr = conv_partial_rows(a, true);
@@ -184,10 +200,35 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
           launch_act_bwd(st.out, st.aux, g, m->draw, rows * st.cout, st.act, P.dtype, s));
     dr = m->draw;
   }
+  if (st.thin == 2) {
+    // dr is planar [n][C_out][H][W]
+    TIMED(si, "bwd.bias_planesum", 0.0, raw_el * es,
+          launch_plane_sums(dr, P.batch, st.cout, (int64_t)st.hc * st.wc, P.dtype, m->partial, s));
+    TIMED(si, "bwd.bias_finalize", 0.0, 0.0, launch_colsum_finalize(m->partial, P.batch, st.cout, grads + st.b_off, s));
+    TIMED(si, "bwd.wgrad_thin", conv_flops, (in_el + raw_el) * es + wel * 4,
+          launch_thin_wgrad(dr, in, m->wgrad_ws, grads + st.w_off, P.batch, st.hin, st.win, st.cout, st.cin, 1, st.up,
+                            P.dtype, s));
+    if (st.needs_dx) {
+      const double full_el = (double)rows * st.cin;
+      TIMED(si, "bwd.dgrad_thin", conv_flops, (raw_el + full_el) * es,
+            launch_thin_in_conv(dr, params + st.w_off, nullptr, st.up ? m->dfull : gnext, nullptr, P.batch, st.hc, st.wc,
+                                st.cout, st.cin, 1, ACT_NONE, P.dtype, s));
+      if (st.up)
+        TIMED(si, "bwd.upsum", 0.0, (full_el + in_el) * es,
+              launch_upsum(m->dfull, gnext, P.batch, st.hin, st.win, st.cin, P.dtype, s));
+    }
+    return AE_OK;
+  }
   // bias gradient: column sums of the conv-output gradient
   TIMED(si, "bwd.bias_colsum", 0.0, raw_el * es, launch_col_stats(dr, rows, st.cout, P.dtype, m->partial, s));
   TIMED(si, "bwd.bias_finalize", 0.0, 0.0,
         launch_colsum_finalize(m->partial, nblocks_for(rows), st.cout, grads + st.b_off, s));
+  if (st.thin == 1) {
+    TIMED(si, "bwd.wgrad_thin", conv_flops, (in_el + raw_el) * es + wel * 4,
+          launch_thin_wgrad(in, dr, m->wgrad_ws, grads + st.w_off, P.batch, st.hc, st.wc, st.cin, st.cout, 0, 0, P.dtype,
+                            s));
+    return AE_OK;   // the first layer needs no input gradient
+  }
   // weight gradient
   WgradArgs wa;
   wa.x = in; wa.dy = dr; wa.dw_canonical = grads + st.w_off;
@@ -494,6 +535,8 @@ int model_get_activation(ae_model* m, int step, float* out_nchw, void* stream) {
   const Step& st = P.steps[step];
   if (step + 1 == (int)P.steps.size() && st.kind == ST_TRANSPOSE)
     return fail(AE_EINVAL, "model_get_activation: the final layout step writes y directly and keeps no copy");
+  if (st.out_planar)  // already [n][C][H][W]: convert only
+    return launch_to_f32_nchw(st.out, out_nchw, P.batch, st.cout * st.hout * st.wout, 1, P.dtype, (hipStream_t)stream);
   return launch_to_f32_nchw(st.out, out_nchw, P.batch, st.cout, st.hout * st.wout, P.dtype, (hipStream_t)stream);
 }
 

@@ -104,15 +104,15 @@ __device__ __forceinline__ void block_col_combine(const float (&acc)[NQ][VEC], i
 
 // partial[b][0][c] = sum over the block's rows of x, partial[b][1][c] = sum of x^2
 template <typename T, int VEC>
-__global__ void k_col_stats(const T* __restrict__ x, int64_t rows, int C, float* __restrict__ partial) {
+__global__ void k_col_stats(const T* __restrict__ x, int64_t rows, int rpb, int C, float* __restrict__ partial) {
   __shared__ float smem[NT * 2 * VEC];
   const int groups = (C + VEC - 1) / VEC;
   const int tpr = groups < NT ? groups : NT;
   const int nrl = NT / tpr;
   const int cg = threadIdx.x % tpr, rl = threadIdx.x / tpr;
   const bool active = rl < nrl;
-  const int64_t r0 = (int64_t)blockIdx.x * kReduceRows;
-  const int64_t r1 = r0 + kReduceRows < rows ? r0 + kReduceRows : rows;
+  const int64_t r0 = (int64_t)blockIdx.x * rpb;
+  const int64_t r1 = r0 + rpb < rows ? r0 + rpb : rows;
   float* pb = partial + (int64_t)blockIdx.x * 2 * C;
   for (int cbase = 0; cbase < C; cbase += tpr * VEC) {
     float acc[2][VEC];
@@ -191,11 +191,12 @@ __global__ void k_post_forward(const T* __restrict__ raw, const float* __restric
   const int Ho = H >> pool, Wo = W >> pool;
   const int64_t total = n * Ho * Wo * groups;
   for (int64_t it = (int64_t)blockIdx.x * NT + threadIdx.x; it < total; it += (int64_t)gridDim.x * NT) {
-    const int c = (int)(it % groups) * VEC;
-    int64_t p = it / groups;
-    const int wo = (int)(p % Wo); p /= Wo;
-    const int ho = (int)(p % Ho);
-    const int64_t b = p / Ho;
+    const unsigned iu = (unsigned)it;             // total < 2^31 (checked by the launcher): 32-bit divisions
+    const int c = (int)(iu % (unsigned)groups) * VEC;
+    unsigned p = iu / (unsigned)groups;
+    const int wo = (int)(p % (unsigned)Wo); p /= (unsigned)Wo;
+    const int ho = (int)(p % (unsigned)Ho);
+    const int64_t b = p / (unsigned)Ho;
     float sc[VEC], sh[VEC];
     if (bn_vec) { load_f32<VEC>(bn_vec + c, sc); load_f32<VEC>(bn_vec + C + c, sh); }
     else {
@@ -280,7 +281,7 @@ struct PostBwdWindow {
 template <typename T, int VEC>
 __global__ void k_post_bwd_reduce(const T* __restrict__ raw, const T* __restrict__ dout,
                                   const float* __restrict__ bn_vec, int64_t n, int H, int W, int C, int act, int pool,
-                                  float* __restrict__ partial) {
+                                  int rpb, float* __restrict__ partial) {
   __shared__ float smem[NT * 2 * VEC];
   const int Ho = H >> pool, Wo = W >> pool;
   const int64_t rows = n * Ho * Wo;
@@ -289,8 +290,8 @@ __global__ void k_post_bwd_reduce(const T* __restrict__ raw, const T* __restrict
   const int nrl = NT / tpr;
   const int cg = threadIdx.x % tpr, rl = threadIdx.x / tpr;
   const bool active = rl < nrl;
-  const int64_t r0 = (int64_t)blockIdx.x * kReduceRows;
-  const int64_t r1 = r0 + kReduceRows < rows ? r0 + kReduceRows : rows;
+  const int64_t r0 = (int64_t)blockIdx.x * rpb;
+  const int64_t r1 = r0 + rpb < rows ? r0 + rpb : rows;
   float* pb = partial + (int64_t)blockIdx.x * 2 * C;
   for (int cbase = 0; cbase < C; cbase += tpr * VEC) {
     float acc[2][VEC];
@@ -299,9 +300,10 @@ __global__ void k_post_bwd_reduce(const T* __restrict__ raw, const T* __restrict
     const int c = cbase + cg * VEC;
     if (active && c < C) {
       for (int64_t r = r0 + rl; r < r1; r += nrl) {
-        const int wo = (int)(r % Wo);
-        const int ho = (int)((r / Wo) % Ho);
-        const int64_t b = r / ((int64_t)Wo * Ho);
+        const unsigned ru = (unsigned)r;              // rows < 2^31 (checked by the launcher)
+        const int wo = (int)(ru % (unsigned)Wo);
+        const int ho = (int)((ru / (unsigned)Wo) % (unsigned)Ho);
+        const int64_t b = ru / ((unsigned)Wo * (unsigned)Ho);
         PostBwdWindow<T, VEC> win;
         win.compute(raw, dout, bn_vec, b, ho, wo, H, W, C, c, act, pool);
         const int nq = pool ? 4 : 1;
@@ -345,11 +347,12 @@ __global__ void k_post_bwd_apply(const T* __restrict__ raw, const T* __restrict_
   const int Ho = H >> pool, Wo = W >> pool;
   const int64_t total = n * Ho * Wo * groups;
   for (int64_t it = (int64_t)blockIdx.x * NT + threadIdx.x; it < total; it += (int64_t)gridDim.x * NT) {
-    const int c = (int)(it % groups) * VEC;
-    int64_t p = it / groups;
-    const int wo = (int)(p % Wo); p /= Wo;
-    const int ho = (int)(p % Ho);
-    const int64_t b = p / Ho;
+    const unsigned iu = (unsigned)it;             // total < 2^31 (checked by the launcher): 32-bit divisions
+    const int c = (int)(iu % (unsigned)groups) * VEC;
+    unsigned p = iu / (unsigned)groups;
+    const int wo = (int)(p % (unsigned)Wo); p /= (unsigned)Wo;
+    const int ho = (int)(p % (unsigned)Ho);
+    const int64_t b = p / (unsigned)Ho;
     PostBwdWindow<T, VEC> win;
     win.compute(raw, dout, bn_vec, b, ho, wo, H, W, C, c, act, pool);
     float sc[VEC], c1[VEC], c2[VEC];
@@ -392,11 +395,12 @@ __global__ void k_upsum(const T* __restrict__ dfull, T* __restrict__ dx, int64_t
   const int groups = C / VEC;
   const int64_t total = n * H * W * groups;
   for (int64_t it = (int64_t)blockIdx.x * NT + threadIdx.x; it < total; it += (int64_t)gridDim.x * NT) {
-    const int c = (int)(it % groups) * VEC;
-    int64_t p = it / groups;
-    const int j = (int)(p % W); p /= W;
-    const int i = (int)(p % H);
-    const int64_t b = p / H;
+    const unsigned iu = (unsigned)it;
+    const int c = (int)(iu % (unsigned)groups) * VEC;
+    unsigned p = iu / (unsigned)groups;
+    const int j = (int)(p % (unsigned)W); p /= (unsigned)W;
+    const int i = (int)(p % (unsigned)H);
+    const int64_t b = p / (unsigned)H;
     float acc[VEC];
 #pragma unroll
     for (int v = 0; v < VEC; ++v) acc[v] = 0.0f;
@@ -471,9 +475,10 @@ int launch_pack_weights(const float* w, void* wp, int cout, int cin, int k, int 
 }
 
 int launch_col_stats(const void* x, int64_t rows, int c, int dtype, float* partial, hipStream_t s) {
-  int nblocks = (int)((rows + kReduceRows - 1) / kReduceRows);
+  const int rpb = reduce_rows_per_block(rows);
+  const int nblocks = reduce_blocks(rows);
   DISPATCH_T_VEC(dtype, c, hipLaunchKernelGGL((k_col_stats<T, VEC>), dim3(nblocks), dim3(NT), 0, s, (const T*)x, rows,
-                                              c, partial));
+                                              rpb, c, partial));
   return launch_status("col_stats");
 }
 
@@ -488,6 +493,7 @@ int launch_post_forward(const void* raw, const float* bn_vec, void* out, int64_t
                         int pool, int dtype, hipStream_t s) {
   DISPATCH_T_VEC(dtype, c, {
     int64_t items = n * (h >> pool) * (w >> pool) * (c / VEC);
+    if (items >= 0x7FFFFFFF) return fail(AE_EINVAL, "post_forward: tensor too large");
     hipLaunchKernelGGL((k_post_forward<T, VEC>), dim3(grid_for(items)), dim3(NT), 0, s, (const T*)raw, bn_vec, (T*)out,
                        n, h, w, c, act, pool);
   });
@@ -497,9 +503,12 @@ int launch_post_forward(const void* raw, const float* bn_vec, void* out, int64_t
 int launch_post_bwd_reduce(const void* raw, const void* dout, const float* bn_vec, int64_t n, int h, int w, int c,
                            int act, int pool, int dtype, float* partial, hipStream_t s) {
   int64_t rows = n * (h >> pool) * (w >> pool);
-  int nblocks = (int)((rows + kReduceRows - 1) / kReduceRows);
+  if (rows >= 0x7FFFFFFF) return fail(AE_EINVAL, "post_bwd_reduce: tensor too large");
+  const int rpb = reduce_rows_per_block(rows);
+  const int nblocks = reduce_blocks(rows);
   DISPATCH_T_VEC(dtype, c, hipLaunchKernelGGL((k_post_bwd_reduce<T, VEC>), dim3(nblocks), dim3(NT), 0, s,
-                                              (const T*)raw, (const T*)dout, bn_vec, n, h, w, c, act, pool, partial));
+                                              (const T*)raw, (const T*)dout, bn_vec, n, h, w, c, act, pool, rpb,
+                                              partial));
   return launch_status("post_bwd_reduce");
 }
 
@@ -515,6 +524,7 @@ int launch_post_bwd_apply(const void* raw, const void* dout, const float* bn_vec
                           int c, int act, int pool, int has_bn, int dtype, hipStream_t s) {
   DISPATCH_T_VEC(dtype, c, {
     int64_t items = n * (h >> pool) * (w >> pool) * (c / VEC);
+    if (items >= 0x7FFFFFFF) return fail(AE_EINVAL, "post_bwd_apply: tensor too large");
     hipLaunchKernelGGL((k_post_bwd_apply<T, VEC>), dim3(grid_for(items)), dim3(NT), 0, s, (const T*)raw,
                        (const T*)dout, bn_vec, (T*)draw, n, h, w, c, act, pool, has_bn);
   });
@@ -536,6 +546,7 @@ int launch_colsum_finalize(const float* partial, int nblocks, int c, float* out,
 int launch_upsum(const void* dfull, void* dx, int64_t n, int h, int w, int c, int dtype, hipStream_t s) {
   DISPATCH_T_VEC(dtype, c, {
     int64_t items = n * h * w * (c / VEC);
+    if (items >= 0x7FFFFFFF) return fail(AE_EINVAL, "upsum: tensor too large");
     hipLaunchKernelGGL((k_upsum<T, VEC>), dim3(grid_for(items)), dim3(NT), 0, s, (const T*)dfull, (T*)dx, n, h, w, c);
   });
   return launch_status("upsum");

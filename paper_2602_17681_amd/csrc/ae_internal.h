@@ -67,6 +67,8 @@ struct Step {
   float* aux = nullptr;             // binary32 copy of a sigmoid output produced in the conv epilogue (bf16 models):
                                     // y*(1-y) from a bf16-rounded y loses all accuracy where the sigmoid saturates
   bool mfma = false;                // forward uses the MFMA implicit-GEMM kernel
+  int thin = 0;                     // 1: thin-in kernels (input is the planar boundary tensor); 2: thin-out kernels
+  bool out_planar = false;          // `out` is stored planar [n][C][H][W] (thin-out step)
 };
 
 struct Plan {
@@ -88,8 +90,18 @@ struct Plan {
 
 int build_plan(const char* spec, int batch, int dtype, int bn_mode, Plan* plan);
 
-// Rows of a column reduction handled by one block (partial-sum granularity).
+// Rows of a column reduction handled by one block (partial-sum granularity): 256 for
+// large tensors, fewer when that would leave the machine with too few blocks.
 constexpr int kReduceRows = 256;
+inline int reduce_rows_per_block(int64_t rows) {
+  int rpb = kReduceRows;
+  while (rpb > 16 && rows / rpb < 2048) rpb >>= 1;
+  return rpb;
+}
+inline int reduce_blocks(int64_t rows) {
+  const int rpb = reduce_rows_per_block(rows);
+  return (int)((rows + rpb - 1) / rpb);
+}
 
 // ---- launchers (all asynchronous on `s`) -----------------------------------
 // layout / dtype
@@ -119,6 +131,19 @@ int launch_wgrad_direct(const WgradArgs& a, hipStream_t s);
 bool wgrad_mfma_supported(const WgradArgs& a);
 int64_t wgrad_mfma_workspace_floats(int cout, int cin, int k, int64_t rows);
 int launch_wgrad_mfma(const WgradArgs& a, float* workspace, hipStream_t s);  // overwrites dw (no zeroing needed)
+
+// 3x3 convolutions with 1..4 channels on one side (first / last layer); see ae_conv_thin.hip
+bool thin_in_supported(int ct, int cw, int k, int up);
+bool thin_out_supported(int ct, int cw, int k, int dtype);
+int thin_in_partial_rows();
+int launch_thin_in_conv(const void* thin, const float* wcanon, const float* bias, void* out, float* partial, int n,
+                        int h, int w, int ct, int cw, int flip, int act, int dtype, hipStream_t s);
+int launch_thin_out_conv(const void* wide, const float* wcanon, const float* bias, void* out, float* out_f32, int n,
+                         int hc, int wc, int ct, int cw, int up, int act, int dtype, hipStream_t s);
+int64_t thin_wgrad_workspace_floats(int64_t q_pixels, int ct, int cw);
+int launch_thin_wgrad(const void* thin, const void* wide, float* workspace, float* dw_canonical, int n, int hq, int wq,
+                      int ct, int cw, int mode, int up, int dtype, hipStream_t s);
+int launch_plane_sums(const void* x, int64_t n, int c, int64_t hw, int dtype, float* partial, hipStream_t s);
 
 // per-channel reductions and the second pass after a conv
 int launch_col_stats(const void* x, int64_t rows, int c, int dtype, float* partial, hipStream_t s);

@@ -207,6 +207,31 @@ int build_plan(const char* spec, int batch, int dtype, int bn_mode, Plan* plan) 
   if (c > 1 && h * w > 1) add_transpose(h * w, c, (int)toks.size() - 1, c, h, w);
   plan->n_params = off;
 
+  // ---- thin first / last layer: the planar boundary tensor is read / written by the conv itself
+  {
+    std::vector<Step>& S = plan->steps;
+    int fc = -1, lc = -1;
+    for (size_t q = 0; q < S.size(); ++q)
+      if (S[q].kind == ST_CONV) { if (fc < 0) fc = (int)q; lc = (int)q; }
+    if (fc >= 0 && (fc == 0 || (fc == 1 && S[0].kind == ST_TRANSPOSE && S[0].last_token == -1))) {
+      Step& st = S[fc];
+      if (st.cin <= 4 && thin_in_supported(st.cin, st.cout, st.k, st.up)) {
+        st.thin = 1;
+        if (fc == 1) { S.erase(S.begin()); --lc; }
+      }
+    }
+    if (lc >= 0) {
+      const bool tail_ok = lc == (int)S.size() - 1 || (lc == (int)S.size() - 2 && S.back().kind == ST_TRANSPOSE);
+      Step& st = S[lc];
+      if (tail_ok && st.thin == 0 && !st.has_bn && !st.pool && st.cout <= 4 && thin_out_supported(st.cout, st.cin, st.k, dtype) &&
+          thin_in_supported(st.cout, st.cin, st.k, 0)) {
+        st.thin = 2;
+        st.out_planar = true;
+        if (lc == (int)S.size() - 2) { st.last_token = S.back().last_token; S.pop_back(); }
+      }
+    }
+  }
+
   // ---- workspace layout ---------------------------------------------------
   const int64_t es = (int64_t)dtype_size(dtype);
   int64_t total = 0;
@@ -233,14 +258,20 @@ int build_plan(const char* spec, int batch, int dtype, int bn_mode, Plan* plan) 
       st.off_wpack = take(wel * es);
       st.off_wpack_d = take(wel * es);
       if (st.has_bn) st.off_bn = take(6 * (int64_t)st.cout * 4);
-      int64_t blocks = (rows + 63) / 64;               // finest partial-sum granularity any kernel uses
+      int64_t blocks = std::max<int64_t>((rows + 127) / 128, reduce_blocks(rows));  // finest partial-sum granularity
       plan->max_partial_floats = std::max(plan->max_partial_floats, blocks * 2 * std::max(st.cout, st.cin));
       WgradArgs wa;
       wa.x = wa.dy = nullptr; wa.dw_canonical = nullptr;
       wa.n = batch; wa.hc = st.hc; wa.wc = st.wc; wa.cin = st.cin; wa.cout = st.cout; wa.k = st.k; wa.up = st.up;
       wa.dtype = dtype;
-      if (wgrad_mfma_supported(wa))
+      if (st.thin == 1)
+        plan->max_wgrad_floats = std::max(plan->max_wgrad_floats, thin_wgrad_workspace_floats(rows, st.cin, st.cout));
+      else if (st.thin == 2)
+        plan->max_wgrad_floats = std::max(plan->max_wgrad_floats,
+                                          thin_wgrad_workspace_floats(B * st.hin * st.win, st.cout, st.cin));
+      else if (wgrad_mfma_supported(wa))
         plan->max_wgrad_floats = std::max(plan->max_wgrad_floats, wgrad_mfma_workspace_floats(st.cout, st.cin, st.k, rows));
+      if (st.thin == 2) plan->max_partial_floats = std::max(plan->max_partial_floats, B * 2 * (int64_t)st.cout);
     }
   }
   plan->off_grad_a = take(plan->max_act_elems * es);      // gradient ping-pong
