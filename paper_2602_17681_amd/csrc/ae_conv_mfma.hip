@@ -32,23 +32,26 @@ struct IgemmParams {
 };
 
 // ---------------------------------------------------------------------------
-// bf16: BK = 32 elements (64 bytes per row per slab); LDS rows padded to 80 bytes so
-// that the eight rows a ds_read_b128 serves per cycle fall into distinct banks.
+// bf16 kernel.  BK = 32 elements: a slab row is 64 bytes = four 16-byte chunks.  LDS
+// rows are not padded; chunk c of row r is stored in slot c ^ ((r >> 1) & 3), which
+// makes both the 16-byte stores of the loader and the 16-byte fragment reads of the
+// MFMA operands conflict-free.  Global loads run two slabs ahead of the MFMAs through
+// two register sets; LDS is double buffered, one barrier per slab.
 // ---------------------------------------------------------------------------
-template <int BM, int BN>
-__global__ __launch_bounds__(256) void k_igemm_bf16(IgemmParams p) {
+template <int BM, int BN, int WGM, int WGN>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_igemm_bf16(IgemmParams p) {
+  static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
   constexpr int BK = 32;
-  constexpr int LDS = 40;                       // row stride in elements (80 bytes)
-  constexpr int WM = BM / 2, WN = BN / 2;       // wave tile
+  constexpr int WM = BM / WGM, WN = BN / WGN;   // wave tile
   constexpr int MI = WM / 32, NJ = WN / 32;     // 32x32 MFMA tiles per wave
   constexpr int A_CHUNKS = BM * 4 / 256;        // 16-byte chunks per thread per slab
   constexpr int B_CHUNKS = BN * 4 / 256;
-  __shared__ __attribute__((aligned(16))) bf16_t sA[2][BM * LDS];
-  __shared__ __attribute__((aligned(16))) bf16_t sB[2][BN * LDS];
-  __shared__ float sRed[2][2][BN];              // [wave row][sum | sumsq][column]
+  __shared__ __attribute__((aligned(16))) bf16_t sA[2][BM * BK];
+  __shared__ __attribute__((aligned(16))) bf16_t sB[2][BN * BK];
+  __shared__ float sRed[WGM][2][BN];            // [wave row][sum | sumsq][column]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WGN, wn = wave % WGN;
   const int tile_n = blockIdx.x % p.tiles_n;
   const int64_t tile_m = blockIdx.x / p.tiles_n;
   const int64_t m0 = tile_m * BM;
@@ -58,58 +61,85 @@ __global__ __launch_bounds__(256) void k_igemm_bf16(IgemmParams p) {
   const int pad = (p.ksz - 1) >> 1;
   const int Hin = p.Hc >> p.up, Win = p.Wc >> p.up;
 
-  // --- loader bookkeeping: this thread's rows of the A and B slabs
-  const int chunk = tid & 3;                    // which 16 bytes of the 64-byte row
+  // --- loader bookkeeping: thread t moves rows (t>>2) + 64*i, LDS slot t&3 of each
+  const int slot = tid & 3;
+  const int lrow = tid >> 2;
+  const int gchunk = slot ^ ((lrow >> 1) & 3);  // 64*i keeps (row>>1)&3: the same global chunk for every i
   int a_h[A_CHUNKS], a_w[A_CHUNKS];
-  int64_t a_img[A_CHUNKS];                      // element offset of the sample's image, -1 if the row is past M
+  int64_t a_img[A_CHUNKS];                      // element offset of the sample's image
+  bool a_ok[A_CHUNKS];                          // row below M
 #pragma unroll
   for (int i = 0; i < A_CHUNKS; ++i) {
-    const int row = (tid >> 2) + i * 64;
-    const int64_t m = m0 + row;
-    if (m < p.M) {
-      const int w = (int)(m % p.Wc);
-      const int64_t t = m / p.Wc;
-      a_h[i] = (int)(t % p.Hc);
-      a_w[i] = w;
-      a_img[i] = (t / p.Hc) * (int64_t)Hin * Win * p.Cin;
-    } else {
-      a_h[i] = 0; a_w[i] = 0; a_img[i] = -1;
-    }
+    const int64_t m = m0 + lrow + i * 64;
+    a_ok[i] = m < p.M;
+    const unsigned mu = a_ok[i] ? (unsigned)m : 0u;
+    a_w[i] = (int)(mu % (unsigned)p.Wc);
+    const unsigned t = mu / (unsigned)p.Wc;
+    a_h[i] = (int)(t % (unsigned)p.Hc);
+    a_img[i] = (int64_t)(t / (unsigned)p.Hc) * Hin * Win * p.Cin;
   }
+  // rows past N read the last valid weight row and are zeroed in registers
   const bf16_t* b_ptr[B_CHUNKS];
+  bool b_ok[B_CHUNKS];
 #pragma unroll
   for (int i = 0; i < B_CHUNKS; ++i) {
-    const int row = (tid >> 2) + i * 64;
-    b_ptr[i] = (n0 + row < p.N) ? W + (int64_t)(n0 + row) * p.K + chunk * 8 : nullptr;
+    const int row = n0 + lrow + i * 64;
+    b_ok[i] = row < p.N;
+    b_ptr[i] = W + (int64_t)(b_ok[i] ? row : p.N - 1) * p.K + gchunk * 8;
   }
 
-  uint4 ra[A_CHUNKS], rb[B_CHUNKS];
-  const uint4 zero4 = make_uint4(0u, 0u, 0u, 0u);
-  int rs = 0, ci0 = 0;                          // filter tap and first channel of the slab being loaded
-  auto load_slab = [&](int kt) {
-    const int r = rs / p.ksz, s = rs - r * p.ksz;
-#pragma unroll
-    for (int i = 0; i < A_CHUNKS; ++i) {
-      const int hh = a_h[i] + r - pad, ww = a_w[i] + s - pad;
-      const bool ok = a_img[i] >= 0 && hh >= 0 && hh < p.Hc && ww >= 0 && ww < p.Wc;
-      ra[i] = ok ? *reinterpret_cast<const uint4*>(X + a_img[i] + ((int64_t)(hh >> p.up) * Win + (ww >> p.up)) * p.Cin +
-                                                   ci0 + chunk * 8)
-                 : zero4;
-    }
-#pragma unroll
-    for (int i = 0; i < B_CHUNKS; ++i)
-      rb[i] = b_ptr[i] ? *reinterpret_cast<const uint4*>(b_ptr[i] + (int64_t)kt * BK) : zero4;
-    ci0 += BK;
-    if (ci0 == p.Cin) { ci0 = 0; ++rs; }
-  };
-  auto store_slab = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < A_CHUNKS; ++i)
-      *reinterpret_cast<uint4*>(&sA[buf][((tid >> 2) + i * 64) * LDS + chunk * 8]) = ra[i];
-#pragma unroll
-    for (int i = 0; i < B_CHUNKS; ++i)
-      *reinterpret_cast<uint4*>(&sB[buf][((tid >> 2) + i * 64) * LDS + chunk * 8]) = rb[i];
-  };
+  int rs = 0, ci0 = 0;                          // filter tap and first channel of the next slab to load
+  int kload = 0;                                // index of the next slab to load
+
+  // Every load goes to a valid address (coordinates clamped into the image); what the
+  // zero padding or the ragged edges require is then zeroed in registers.
+#define IGEMM_LOAD(RA, RB)                                                                                   \
+  {                                                                                                          \
+    const int r_ = rs / p.ksz, s_ = rs - r_ * p.ksz;                                                         \
+    _Pragma("unroll") for (int i = 0; i < A_CHUNKS; ++i) {                                                   \
+      const int hh = a_h[i] + r_ - pad, ww = a_w[i] + s_ - pad;                                              \
+      const bool ok = a_ok[i] && hh >= 0 && hh < p.Hc && ww >= 0 && ww < p.Wc;                               \
+      const int hc_ = min(max(hh, 0), p.Hc - 1), wc_ = min(max(ww, 0), p.Wc - 1);                            \
+      uint4 v = *reinterpret_cast<const uint4*>(X + a_img[i] +                                               \
+                                                ((int64_t)(hc_ >> p.up) * Win + (wc_ >> p.up)) * p.Cin + ci0 + \
+                                                gchunk * 8);                                                 \
+      if (!ok) { v.x = 0u; v.y = 0u; v.z = 0u; v.w = 0u; }                                                   \
+      RA[i] = v;                                                                                             \
+    }                                                                                                        \
+    _Pragma("unroll") for (int i = 0; i < B_CHUNKS; ++i) {                                                   \
+      uint4 v = *reinterpret_cast<const uint4*>(b_ptr[i] + (int64_t)kload * BK);                             \
+      if (!b_ok[i]) { v.x = 0u; v.y = 0u; v.z = 0u; v.w = 0u; }                                              \
+      RB[i] = v;                                                                                             \
+    }                                                                                                        \
+    ci0 += BK;                                                                                               \
+    if (ci0 == p.Cin) { ci0 = 0; ++rs; }                                                                     \
+    ++kload;                                                                                                 \
+  }
+#define IGEMM_STORE(BUF, RA, RB)                                                                             \
+  {                                                                                                          \
+    _Pragma("unroll") for (int i = 0; i < A_CHUNKS; ++i)                                                     \
+        *reinterpret_cast<uint4*>(&sA[BUF][(lrow + i * 64) * BK + slot * 8]) = RA[i];                        \
+    _Pragma("unroll") for (int i = 0; i < B_CHUNKS; ++i)                                                     \
+        *reinterpret_cast<uint4*>(&sB[BUF][(lrow + i * 64) * BK + slot * 8]) = RB[i];                        \
+  }
+  // fragment of row r, k-chunk c (of 4): slot c ^ ((r>>1)&3)
+#define IGEMM_COMPUTE(BUF)                                                                                   \
+  {                                                                                                          \
+    _Pragma("unroll") for (int ks = 0; ks < BK / 16; ++ks) {                                                 \
+      bf16x8 a[MI], b[NJ];                                                                                   \
+      _Pragma("unroll") for (int i = 0; i < MI; ++i) {                                                       \
+        const int r = wm * WM + i * 32 + frag_row;                                                           \
+        a[i] = *reinterpret_cast<const bf16x8*>(&sA[BUF][r * BK + (((ks * 2 + frag_c) ^ ((r >> 1) & 3)) * 8)]); \
+      }                                                                                                      \
+      _Pragma("unroll") for (int j = 0; j < NJ; ++j) {                                                       \
+        const int r = wn * WN + j * 32 + frag_row;                                                           \
+        b[j] = *reinterpret_cast<const bf16x8*>(&sB[BUF][r * BK + (((ks * 2 + frag_c) ^ ((r >> 1) & 3)) * 8)]); \
+      }                                                                                                      \
+      _Pragma("unroll") for (int i = 0; i < MI; ++i)                                                         \
+        _Pragma("unroll") for (int j = 0; j < NJ; ++j)                                                       \
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);             \
+    }                                                                                                        \
+  }
 
   floatx16 acc[MI][NJ];
 #pragma unroll
@@ -120,30 +150,28 @@ __global__ __launch_bounds__(256) void k_igemm_bf16(IgemmParams p) {
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
   const int KT = p.K / BK;
-  load_slab(0);
-  store_slab(0);
+  const int frag_row = lane & 31, frag_c = lane >> 5;
+  uint4 ra0[A_CHUNKS], rb0[B_CHUNKS], ra1[A_CHUNKS], rb1[B_CHUNKS];
+  IGEMM_LOAD(ra0, rb0);
+  if (KT > 1) IGEMM_LOAD(ra1, rb1);
+  IGEMM_STORE(0, ra0, rb0);
   __syncthreads();
-  const int frag_row = lane & 31, frag_k = (lane >> 5) * 8;
-  for (int kt = 0; kt < KT; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < KT) load_slab(kt + 1);
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 a[MI], b[NJ];
-#pragma unroll
-      for (int i = 0; i < MI; ++i)
-        a[i] = *reinterpret_cast<const bf16x8*>(&sA[buf][(wm * WM + i * 32 + frag_row) * LDS + ks * 16 + frag_k]);
-#pragma unroll
-      for (int j = 0; j < NJ; ++j)
-        b[j] = *reinterpret_cast<const bf16x8*>(&sB[buf][(wn * WN + j * 32 + frag_row) * LDS + ks * 16 + frag_k]);
-#pragma unroll
-      for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < NJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < KT) store_slab(buf ^ 1);
+  for (int kt = 0; kt < KT; kt += 2) {
+    // even slab: LDS buffer 0; register set 1 holds slab kt+1; set 0 is free
+    if (kt + 2 < KT) IGEMM_LOAD(ra0, rb0);
+    IGEMM_COMPUTE(0);
+    if (kt + 1 < KT) IGEMM_STORE(1, ra1, rb1);
+    __syncthreads();
+    if (kt + 1 >= KT) break;
+    // odd slab: LDS buffer 1; register set 0 holds slab kt+2; set 1 is free
+    if (kt + 3 < KT) IGEMM_LOAD(ra1, rb1);
+    IGEMM_COMPUTE(1);
+    if (kt + 2 < KT) IGEMM_STORE(0, ra0, rb0);
     __syncthreads();
   }
+#undef IGEMM_LOAD
+#undef IGEMM_STORE
+#undef IGEMM_COMPUTE
 
   // --- epilogue.  Accumulator element e of lane l in tile (i,j):
   //     row = wm*WM + i*32 + (e/4)*8 + (l/32)*4 + e%4,  column = wn*WN + j*32 + l%32
@@ -183,12 +211,24 @@ __global__ __launch_bounds__(256) void k_igemm_bf16(IgemmParams p) {
     __syncthreads();
     for (int i = tid; i < 2 * BN; i += 256) {
       const int q = i / BN, c = i - q * BN;
-      if (n0 + c < p.N) p.partial[(tile_m * 2 + q) * p.N + n0 + c] = sRed[0][q][c] + sRed[1][q][c];
+      float t = 0.0f;
+#pragma unroll
+      for (int g = 0; g < WGM; ++g) t += sRed[g][q][c];
+      if (n0 + c < p.N) p.partial[(tile_m * 2 + q) * p.N + n0 + c] = t;
     }
   }
 }
 
-int tile_n_for(int cout) { return cout > 64 ? 128 : 64; }
+struct IgemmTile { int bm, bn; };
+
+// Largest tile that still gives every compute unit about two workgroups.
+IgemmTile pick_tile(int64_t M, int cout) {
+  const int bn = cout > 64 ? 128 : 64;
+  const int64_t tiles_n = (cout + bn - 1) / bn;
+  int bm = bn == 64 ? 256 : 128;               // 256x128 does not fit the register budget of two waves per SIMD
+  if (((M + 255) / 256) * tiles_n < 512) bm = 128;
+  return IgemmTile{bm, bn};
+}
 
 }  // namespace
 
@@ -196,11 +236,13 @@ bool conv_mfma_supported(const ConvArgs& a) {
   if (a.dtype != AE_BF16) return false;
   if (a.cin % 32 != 0 || a.cout < 32) return false;
   const int64_t M = (int64_t)a.n * a.hc * a.wc;
-  const int64_t tiles = ((M + 127) / 128) * ((a.cout + tile_n_for(a.cout) - 1) / tile_n_for(a.cout));
-  return tiles < 0x7FFFFFFF;
+  return M * ((a.cout + 63) / 64) / 128 < 0x7FFFFFFF && M < 0x7FFFFFFF;
 }
 
-int conv_partial_rows(const ConvArgs&, bool mfma) { return mfma ? 128 : kReduceRows; }
+int conv_partial_rows(const ConvArgs& a, bool mfma) {
+  if (!mfma) return kReduceRows;
+  return pick_tile((int64_t)a.n * a.hc * a.wc, a.cout).bm;
+}
 
 int launch_conv_mfma(const ConvArgs& a, hipStream_t s) {
   if (!conv_mfma_supported(a)) return fail(AE_EINVAL, "conv_mfma: shape not supported");
@@ -209,12 +251,14 @@ int launch_conv_mfma(const ConvArgs& a, hipStream_t s) {
   p.M = (int64_t)a.n * a.hc * a.wc;
   p.N = a.cout; p.K = a.k * a.k * a.cin;
   p.Hc = a.hc; p.Wc = a.wc; p.Cin = a.cin; p.ksz = a.k; p.up = a.up; p.act = a.act;
-  const int bn = tile_n_for(a.cout);
-  p.tiles_n = (a.cout + bn - 1) / bn;
-  const int64_t tiles_m = (p.M + 127) / 128;
+  const IgemmTile t = pick_tile(p.M, a.cout);
+  p.tiles_n = (a.cout + t.bn - 1) / t.bn;
+  const int64_t tiles_m = (p.M + t.bm - 1) / t.bm;
   dim3 grid((unsigned)(tiles_m * p.tiles_n));
-  if (bn == 128) hipLaunchKernelGGL((k_igemm_bf16<128, 128>), grid, dim3(256), 0, s, p);
-  else hipLaunchKernelGGL((k_igemm_bf16<128, 64>), grid, dim3(256), 0, s, p);
+  if (t.bm == 256 && t.bn == 128) hipLaunchKernelGGL((k_igemm_bf16<256, 128, 2, 2>), grid, dim3(256), 0, s, p);
+  else if (t.bm == 256) hipLaunchKernelGGL((k_igemm_bf16<256, 64, 4, 1>), grid, dim3(256), 0, s, p);
+  else if (t.bn == 128) hipLaunchKernelGGL((k_igemm_bf16<128, 128, 2, 2>), grid, dim3(256), 0, s, p);
+  else hipLaunchKernelGGL((k_igemm_bf16<128, 64, 2, 2>), grid, dim3(256), 0, s, p);
   return launch_status("conv_mfma");
 }
 

@@ -233,15 +233,17 @@ __device__ __forceinline__ float act_grad(float pre, float a, int act) {
 
 // Backward of the second pass, shared by the reduction and the apply kernels: for
 // one output pixel (a 2x2 window when pooling) and VEC channels, find the routed
-// gradient dy_j at each raw position j and xhat_j.
-template <typename T, int VEC>
+// gradient dy_j at each raw position j and xhat_j.  Everything is unrolled at compile
+// time so that the per-position arrays stay in registers.
+template <typename T, int VEC, bool POOL>
 struct PostBwdWindow {
-  float dy[4][VEC];
-  float xh[4][VEC];
+  static constexpr int NQ = POOL ? 4 : 1;
+  float dy[NQ][VEC];
+  float xh[NQ][VEC];
   __device__ __forceinline__ void compute(const T* __restrict__ raw, const T* __restrict__ dout,
                                           const float* __restrict__ bn_vec, int64_t b, int ho, int wo, int H, int W,
-                                          int C, int c, int act, int pool) {
-    const int Ho = H >> pool, Wo = W >> pool;
+                                          int C, int c, int act) {
+    const int Ho = POOL ? H >> 1 : H, Wo = POOL ? W >> 1 : W;
     float sc[VEC], sh[VEC], mu[VEC], is[VEC];
     if (bn_vec) {
       load_f32<VEC>(bn_vec + c, sc); load_f32<VEC>(bn_vec + C + c, sh);
@@ -252,38 +254,35 @@ struct PostBwdWindow {
     }
     float g[VEC];
     load_vec<T, VEC>(dout + ((b * Ho + ho) * Wo + wo) * C + c, g);
-    const int nq = pool ? 4 : 1;
     float best[VEC], dbest[VEC];
     int arg[VEC];
-    for (int q = 0; q < nq; ++q) {
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
       float v[VEC];
-      const int hh = pool ? 2 * ho + (q >> 1) : ho, ww = pool ? 2 * wo + (q & 1) : wo;
+      const int hh = POOL ? 2 * ho + (q >> 1) : ho, ww = POOL ? 2 * wo + (q & 1) : wo;
       load_vec<T, VEC>(raw + ((b * H + hh) * W + ww) * C + c, v);
 #pragma unroll
       for (int j = 0; j < VEC; ++j) {
-        float pre = fmaf(sc[j], v[j], sh[j]);
-        float a = apply_act(pre, act);
+        const float pre = fmaf(sc[j], v[j], sh[j]);
+        const float a = apply_act(pre, act);
         xh[q][j] = (v[j] - mu[j]) * is[j];
-        dy[q][j] = 0.0f;
         if (q == 0 || a > best[j]) { best[j] = a; arg[j] = q; dbest[j] = act_grad(pre, a, act); }
       }
     }
 #pragma unroll
-    for (int j = 0; j < VEC; ++j) {
+    for (int q = 0; q < NQ; ++q)
 #pragma unroll
-      for (int q = 0; q < 4; ++q)
-        if (q < nq && arg[j] == q) dy[q][j] = g[j] * dbest[j];
-    }
+      for (int j = 0; j < VEC; ++j) dy[q][j] = (arg[j] == q) ? g[j] * dbest[j] : 0.0f;
   }
 };
 
 // partial[b][0][c] = sum dy, partial[b][1][c] = sum dy*xhat over the block's output pixels
-template <typename T, int VEC>
+template <typename T, int VEC, bool POOL>
 __global__ void k_post_bwd_reduce(const T* __restrict__ raw, const T* __restrict__ dout,
-                                  const float* __restrict__ bn_vec, int64_t n, int H, int W, int C, int act, int pool,
+                                  const float* __restrict__ bn_vec, int64_t n, int H, int W, int C, int act,
                                   int rpb, float* __restrict__ partial) {
   __shared__ float smem[NT * 2 * VEC];
-  const int Ho = H >> pool, Wo = W >> pool;
+  const int Ho = POOL ? H >> 1 : H, Wo = POOL ? W >> 1 : W;
   const int64_t rows = n * Ho * Wo;
   const int groups = (C + VEC - 1) / VEC;
   const int tpr = groups < NT ? groups : NT;
@@ -304,12 +303,12 @@ __global__ void k_post_bwd_reduce(const T* __restrict__ raw, const T* __restrict
         const int wo = (int)(ru % (unsigned)Wo);
         const int ho = (int)((ru / (unsigned)Wo) % (unsigned)Ho);
         const int64_t b = ru / ((unsigned)Wo * (unsigned)Ho);
-        PostBwdWindow<T, VEC> win;
-        win.compute(raw, dout, bn_vec, b, ho, wo, H, W, C, c, act, pool);
-        const int nq = pool ? 4 : 1;
-        for (int q = 0; q < nq; ++q)
+        PostBwdWindow<T, VEC, POOL> win;
+        win.compute(raw, dout, bn_vec, b, ho, wo, H, W, C, c, act);
 #pragma unroll
-          for (int j = 0; j < VEC; ++j) { acc[0][j] += win.dy[q][j]; acc[1][j] += win.dy[q][j] * win.xh[q][j]; }
+        for (int q = 0; q < PostBwdWindow<T, VEC, POOL>::NQ; ++q)
+#pragma unroll
+          for (int j = 0; j < VEC; ++j) { acc[0][j] += win.dy[q][j]; acc[1][j] = fmaf(win.dy[q][j], win.xh[q][j], acc[1][j]); }
       }
     }
     block_col_combine<VEC, 2>(acc, cg, rl, nrl, tpr, cbase, C, pb, smem, active);
@@ -339,12 +338,12 @@ __global__ void k_bn_bwd_finalize(const float* __restrict__ partial, int nblocks
 }
 
 // draw_j = scale*(dy_j - c1 - xhat_j*c2) with batch-norm, dy_j without
-template <typename T, int VEC>
+template <typename T, int VEC, bool POOL>
 __global__ void k_post_bwd_apply(const T* __restrict__ raw, const T* __restrict__ dout,
                                  const float* __restrict__ bn_vec, T* __restrict__ draw, int64_t n, int H, int W,
-                                 int C, int act, int pool, int has_bn) {
+                                 int C, int act, int has_bn) {
   const int groups = C / VEC;
-  const int Ho = H >> pool, Wo = W >> pool;
+  const int Ho = POOL ? H >> 1 : H, Wo = POOL ? W >> 1 : W;
   const int64_t total = n * Ho * Wo * groups;
   for (int64_t it = (int64_t)blockIdx.x * NT + threadIdx.x; it < total; it += (int64_t)gridDim.x * NT) {
     const unsigned iu = (unsigned)it;             // total < 2^31 (checked by the launcher): 32-bit divisions
@@ -353,17 +352,17 @@ __global__ void k_post_bwd_apply(const T* __restrict__ raw, const T* __restrict_
     const int wo = (int)(p % (unsigned)Wo); p /= (unsigned)Wo;
     const int ho = (int)(p % (unsigned)Ho);
     const int64_t b = p / (unsigned)Ho;
-    PostBwdWindow<T, VEC> win;
-    win.compute(raw, dout, bn_vec, b, ho, wo, H, W, C, c, act, pool);
+    PostBwdWindow<T, VEC, POOL> win;
+    win.compute(raw, dout, bn_vec, b, ho, wo, H, W, C, c, act);
     float sc[VEC], c1[VEC], c2[VEC];
     if (has_bn) { load_f32<VEC>(bn_vec + c, sc); load_f32<VEC>(bn_vec + 4 * C + c, c1); load_f32<VEC>(bn_vec + 5 * C + c, c2); }
-    const int nq = pool ? 4 : 1;
-    for (int q = 0; q < nq; ++q) {
+#pragma unroll
+    for (int q = 0; q < PostBwdWindow<T, VEC, POOL>::NQ; ++q) {
       float o[VEC];
 #pragma unroll
       for (int j = 0; j < VEC; ++j)
         o[j] = has_bn ? sc[j] * (win.dy[q][j] - c1[j] - win.xh[q][j] * c2[j]) : win.dy[q][j];
-      const int hh = pool ? 2 * ho + (q >> 1) : ho, ww = pool ? 2 * wo + (q & 1) : wo;
+      const int hh = POOL ? 2 * ho + (q >> 1) : ho, ww = POOL ? 2 * wo + (q & 1) : wo;
       store_vec<T, VEC>(draw + ((b * H + hh) * W + ww) * C + c, o);
     }
   }
@@ -506,9 +505,14 @@ int launch_post_bwd_reduce(const void* raw, const void* dout, const float* bn_ve
   if (rows >= 0x7FFFFFFF) return fail(AE_EINVAL, "post_bwd_reduce: tensor too large");
   const int rpb = reduce_rows_per_block(rows);
   const int nblocks = reduce_blocks(rows);
-  DISPATCH_T_VEC(dtype, c, hipLaunchKernelGGL((k_post_bwd_reduce<T, VEC>), dim3(nblocks), dim3(NT), 0, s,
-                                              (const T*)raw, (const T*)dout, bn_vec, n, h, w, c, act, pool, rpb,
-                                              partial));
+  DISPATCH_T_VEC(dtype, c, {
+    if (pool)
+      hipLaunchKernelGGL((k_post_bwd_reduce<T, VEC, true>), dim3(nblocks), dim3(NT), 0, s, (const T*)raw,
+                         (const T*)dout, bn_vec, n, h, w, c, act, rpb, partial);
+    else
+      hipLaunchKernelGGL((k_post_bwd_reduce<T, VEC, false>), dim3(nblocks), dim3(NT), 0, s, (const T*)raw,
+                         (const T*)dout, bn_vec, n, h, w, c, act, rpb, partial);
+  });
   return launch_status("post_bwd_reduce");
 }
 
@@ -525,8 +529,12 @@ int launch_post_bwd_apply(const void* raw, const void* dout, const float* bn_vec
   DISPATCH_T_VEC(dtype, c, {
     int64_t items = n * (h >> pool) * (w >> pool) * (c / VEC);
     if (items >= 0x7FFFFFFF) return fail(AE_EINVAL, "post_bwd_apply: tensor too large");
-    hipLaunchKernelGGL((k_post_bwd_apply<T, VEC>), dim3(grid_for(items)), dim3(NT), 0, s, (const T*)raw,
-                       (const T*)dout, bn_vec, (T*)draw, n, h, w, c, act, pool, has_bn);
+    if (pool)
+      hipLaunchKernelGGL((k_post_bwd_apply<T, VEC, true>), dim3(grid_for(items)), dim3(NT), 0, s, (const T*)raw,
+                         (const T*)dout, bn_vec, (T*)draw, n, h, w, c, act, has_bn);
+    else
+      hipLaunchKernelGGL((k_post_bwd_apply<T, VEC, false>), dim3(grid_for(items)), dim3(NT), 0, s, (const T*)raw,
+                         (const T*)dout, bn_vec, (T*)draw, n, h, w, c, act, has_bn);
   });
   return launch_status("post_bwd_apply");
 }
