@@ -132,7 +132,15 @@ int forward_conv(ae_model* m, int si, Step& st, const float* params, const void*
   int nblk = 0;
   const double conv_flops = 2.0 * raw_el * st.cin * st.k * st.k;
   const double conv_bytes = (in_el + raw_el + wel) * es;
-  if (st.thin == 1) {
+  if (st.thin == 1 && thin_in_mfma_supported(st.cin, st.cout, st.k, st.up, P.dtype) && !a.y_aux) {
+    if (st.has_bn && P.bn_mode == 0) {
+      a.partial = m->partial;
+      nblk = thin_in_mfma_blocks(P.batch, st.hc, st.wc);
+    }
+    TIMED(si, "fwd.conv_thin_in_mfma", conv_flops, conv_bytes,
+          launch_thin_in_mfma(in, params + st.w_off, a.bias, a.y, a.partial, P.batch, st.hc, st.wc, st.cin, st.cout, 0,
+                              a.act, s));
+  } else if (st.thin == 1) {
     if (st.has_bn && P.bn_mode == 0) {
       a.partial = m->partial;
       nblk = (int)((rows + thin_in_partial_rows() - 1) / thin_in_partial_rows());
@@ -210,9 +218,14 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
                             P.dtype, s));
     if (st.needs_dx) {
       const double full_el = (double)rows * st.cin;
-      TIMED(si, "bwd.dgrad_thin", conv_flops, (raw_el + full_el) * es,
-            launch_thin_in_conv(dr, params + st.w_off, nullptr, st.up ? m->dfull : gnext, nullptr, P.batch, st.hc, st.wc,
-                                st.cout, st.cin, 1, ACT_NONE, P.dtype, s));
+      if (thin_in_mfma_supported(st.cout, st.cin, st.k, 0, P.dtype))
+        TIMED(si, "bwd.dgrad_thin_mfma", conv_flops, (raw_el + full_el) * es,
+              launch_thin_in_mfma(dr, params + st.w_off, nullptr, st.up ? m->dfull : gnext, nullptr, P.batch, st.hc,
+                                  st.wc, st.cout, st.cin, 1, ACT_NONE, s));
+      else
+        TIMED(si, "bwd.dgrad_thin", conv_flops, (raw_el + full_el) * es,
+              launch_thin_in_conv(dr, params + st.w_off, nullptr, st.up ? m->dfull : gnext, nullptr, P.batch, st.hc,
+                                  st.wc, st.cout, st.cin, 1, ACT_NONE, P.dtype, s));
       if (st.up)
         TIMED(si, "bwd.upsum", 0.0, (full_el + in_el) * es,
               launch_upsum(m->dfull, gnext, P.batch, st.hin, st.win, st.cin, P.dtype, s));

@@ -39,7 +39,7 @@ struct IgemmParams {
 // two register sets; LDS is double buffered, one barrier per slab.
 // ---------------------------------------------------------------------------
 template <int BM, int BN, int WGM, int WGN>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_igemm_bf16(IgemmParams p) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k_igemm_bf16(IgemmParams p) {
   static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
   constexpr int BK = 32;
   constexpr int WM = BM / WGM, WN = BN / WGN;   // wave tile
@@ -307,7 +307,7 @@ __device__ __forceinline__ bf16x8 lds_tr_frag(const bf16_t* base0, const bf16_t*
 }
 
 template <int BM, int BN>
-__global__ __launch_bounds__(256) void k_wgrad_bf16(WgradParams p) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k_wgrad_bf16(WgradParams p) {
   constexpr int BK = 32;                         // pixels per slab
   constexpr int LA = BM + 16, LB = BN + 16;      // LDS row strides in elements (+32 bytes: 4 rows hit disjoint banks)
   constexpr int WM = BM / 2, WN = BN / 2;
@@ -337,45 +337,64 @@ __global__ __launch_bounds__(256) void k_wgrad_bf16(WgradParams p) {
   const int64_t m_end = (m_begin + p.rows_per_split < p.M) ? m_begin + p.rows_per_split : p.M;
   const int KT = (int)((m_end - m_begin + BK - 1) / BK);
 
-  uint4 ra[A_CHUNKS], rb[B_CHUNKS];
-  const uint4 zero4 = make_uint4(0u, 0u, 0u, 0u);
-  auto load_slab = [&](int kt) {
-    const int64_t mb = m_begin + (int64_t)kt * BK;
-#pragma unroll
-    for (int i = 0; i < A_CHUNKS; ++i) {
-      const int id = tid + i * 256;
-      const int64_t m = mb + id / A_TPR;
-      ra[i] = (m < m_end) ? *reinterpret_cast<const uint4*>(DY + m * p.Cout + co0 + (id % A_TPR) * 8) : zero4;
-    }
-#pragma unroll
-    for (int i = 0; i < B_CHUNKS; ++i) {
-      const int id = tid + i * 256;
-      const int64_t m = mb + id / B_TPR;
-      uint4 v = zero4;
-      if (m < m_end) {
-        const unsigned mm = (unsigned)m;
-        const unsigned w = mm % (unsigned)p.Wc, t = mm / (unsigned)p.Wc;
-        const unsigned h = t % (unsigned)p.Hc, n = t / (unsigned)p.Hc;
-        const int hh = (int)h + r - pad, ww = (int)w + s - pad;
-        if (hh >= 0 && hh < p.Hc && ww >= 0 && ww < p.Wc)
-          v = *reinterpret_cast<const uint4*>(X + (((int64_t)n * Hin + (hh >> p.up)) * Win + (ww >> p.up)) * p.Cin + ci0 +
-                                              (id % B_TPR) * 8);
-      }
-      rb[i] = v;
-    }
-  };
-  auto store_slab = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < A_CHUNKS; ++i) {
-      const int id = tid + i * 256;
-      *reinterpret_cast<uint4*>(&sA[buf][(id / A_TPR) * LA + (id % A_TPR) * 8]) = ra[i];
-    }
-#pragma unroll
-    for (int i = 0; i < B_CHUNKS; ++i) {
-      const int id = tid + i * 256;
-      *reinterpret_cast<uint4*>(&sB[buf][(id / B_TPR) * LB + (id % B_TPR) * 8]) = rb[i];
-    }
-  };
+  // Loads always go to valid addresses (clamped pixel and coordinates); rows past the
+  // split's end and taps that fall into the zero padding are zeroed in registers.
+  int kload = 0;
+#define WGRAD_LOAD(RA, RB)                                                                                   \
+  {                                                                                                          \
+    const int64_t mb = m_begin + (int64_t)kload * BK;                                                        \
+    _Pragma("unroll") for (int i = 0; i < A_CHUNKS; ++i) {                                                   \
+      const int id = tid + i * 256;                                                                          \
+      const int64_t m = mb + id / A_TPR;                                                                     \
+      const bool ok = m < m_end;                                                                             \
+      uint4 v = *reinterpret_cast<const uint4*>(DY + (ok ? m : m_end - 1) * p.Cout + co0 + (id % A_TPR) * 8); \
+      if (!ok) { v.x = 0u; v.y = 0u; v.z = 0u; v.w = 0u; }                                                   \
+      RA[i] = v;                                                                                             \
+    }                                                                                                        \
+    _Pragma("unroll") for (int i = 0; i < B_CHUNKS; ++i) {                                                   \
+      const int id = tid + i * 256;                                                                          \
+      const int64_t m = mb + id / B_TPR;                                                                     \
+      const unsigned mm = (unsigned)(m < m_end ? m : m_end - 1);                                             \
+      const unsigned w = mm % (unsigned)p.Wc, t = mm / (unsigned)p.Wc;                                       \
+      const unsigned h = t % (unsigned)p.Hc, n = t / (unsigned)p.Hc;                                         \
+      const int hh = (int)h + r - pad, ww = (int)w + s - pad;                                                \
+      const bool ok = m < m_end && hh >= 0 && hh < p.Hc && ww >= 0 && ww < p.Wc;                             \
+      const int hc_ = min(max(hh, 0), p.Hc - 1), wc_ = min(max(ww, 0), p.Wc - 1);                            \
+      uint4 v = *reinterpret_cast<const uint4*>(X + (((int64_t)n * Hin + (hc_ >> p.up)) * Win + (wc_ >> p.up)) * p.Cin + \
+                                                ci0 + (id % B_TPR) * 8);                                     \
+      if (!ok) { v.x = 0u; v.y = 0u; v.z = 0u; v.w = 0u; }                                                   \
+      RB[i] = v;                                                                                             \
+    }                                                                                                        \
+    ++kload;                                                                                                 \
+  }
+#define WGRAD_STORE(BUF, RA, RB)                                                                             \
+  {                                                                                                          \
+    _Pragma("unroll") for (int i = 0; i < A_CHUNKS; ++i) {                                                   \
+      const int id = tid + i * 256;                                                                          \
+      *reinterpret_cast<uint4*>(&sA[BUF][(id / A_TPR) * LA + (id % A_TPR) * 8]) = RA[i];                     \
+    }                                                                                                        \
+    _Pragma("unroll") for (int i = 0; i < B_CHUNKS; ++i) {                                                   \
+      const int id = tid + i * 256;                                                                          \
+      *reinterpret_cast<uint4*>(&sB[BUF][(id / B_TPR) * LB + (id % B_TPR) * 8]) = RB[i];                     \
+    }                                                                                                        \
+  }
+#define WGRAD_COMPUTE(BUF)                                                                                   \
+  {                                                                                                          \
+    _Pragma("unroll") for (int ks = 0; ks < BK / 16; ++ks) {                                                 \
+      bf16x8 a[MI], bb[NJ];                                                                                  \
+      _Pragma("unroll") for (int i = 0; i < MI; ++i) {                                                       \
+        const bf16_t* q = &sA[BUF][(ks * 16 + t_pix) * LA + wm * WM + i * 32 + t_ch];                        \
+        a[i] = lds_tr_frag(q, q + 4 * LA);                                                                   \
+      }                                                                                                      \
+      _Pragma("unroll") for (int j = 0; j < NJ; ++j) {                                                       \
+        const bf16_t* q = &sB[BUF][(ks * 16 + t_pix) * LB + wn * WN + j * 32 + t_ch];                        \
+        bb[j] = lds_tr_frag(q, q + 4 * LB);                                                                  \
+      }                                                                                                      \
+      _Pragma("unroll") for (int i = 0; i < MI; ++i)                                                         \
+        _Pragma("unroll") for (int j = 0; j < NJ; ++j)                                                       \
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bb[j], acc[i][j], 0, 0, 0);            \
+    }                                                                                                        \
+  }
 
   floatx16 acc[MI][NJ];
 #pragma unroll
@@ -392,35 +411,26 @@ __global__ __launch_bounds__(256) void k_wgrad_bf16(WgradParams p) {
   const int t_pix = 8 * (grp >> 1) + (sl >> 2);
   const int t_ch = 16 * (grp & 1) + 4 * (sl & 3);
 
-  if (KT > 0) {
-    load_slab(0);
-    store_slab(0);
-  }
+  // KT >= 1: every split owns at least one pixel (the host sizes the splits that way)
+  uint4 ra0[A_CHUNKS], rb0[B_CHUNKS], ra1[A_CHUNKS], rb1[B_CHUNKS];
+  WGRAD_LOAD(ra0, rb0);
+  if (KT > 1) WGRAD_LOAD(ra1, rb1);
+  WGRAD_STORE(0, ra0, rb0);
   __syncthreads();
-  for (int kt = 0; kt < KT; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < KT) load_slab(kt + 1);
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 a[MI], bb[NJ];
-#pragma unroll
-      for (int i = 0; i < MI; ++i) {
-        const bf16_t* q = &sA[buf][(ks * 16 + t_pix) * LA + wm * WM + i * 32 + t_ch];
-        a[i] = lds_tr_frag(q, q + 4 * LA);
-      }
-#pragma unroll
-      for (int j = 0; j < NJ; ++j) {
-        const bf16_t* q = &sB[buf][(ks * 16 + t_pix) * LB + wn * WN + j * 32 + t_ch];
-        bb[j] = lds_tr_frag(q, q + 4 * LB);
-      }
-#pragma unroll
-      for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < NJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bb[j], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < KT) store_slab(buf ^ 1);
+  for (int kt = 0; kt < KT; kt += 2) {
+    if (kt + 2 < KT) WGRAD_LOAD(ra0, rb0);
+    WGRAD_COMPUTE(0);
+    if (kt + 1 < KT) WGRAD_STORE(1, ra1, rb1);
+    __syncthreads();
+    if (kt + 1 >= KT) break;
+    if (kt + 3 < KT) WGRAD_LOAD(ra1, rb1);
+    WGRAD_COMPUTE(1);
+    if (kt + 2 < KT) WGRAD_STORE(0, ra0, rb0);
     __syncthreads();
   }
+#undef WGRAD_LOAD
+#undef WGRAD_STORE
+#undef WGRAD_COMPUTE
 
   // partial[split][co][tap*Cin + ci]
   float* __restrict__ P = p.partial + (int64_t)split * p.Cout * p.K;

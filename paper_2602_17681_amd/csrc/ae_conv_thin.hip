@@ -65,23 +65,38 @@ __global__ __launch_bounds__(NT) void k_thin_in_conv(const T* __restrict__ thin,
     const int w = (int)(mu % (unsigned)W);
     const int h = (int)((mu / (unsigned)W) % (unsigned)H);
     const int64_t n = mu / ((unsigned)H * (unsigned)W);
-    float acc[4] = {bs[0], bs[1], bs[2], bs[3]};
+    // all 9*CT loads first, unconditionally and from clamped (valid) coordinates, so that
+    // they are in flight together; the zero padding is applied to the loaded values
+    float xv[CT * 9];
+    int roff[3], coff[3];
+    bool rok[3], cok[3];
+#pragma unroll
+    for (int t = 0; t < 3; ++t) {
+      const int hh = h + t - 1, ww = w + t - 1;
+      rok[t] = hh >= 0 && hh < H;
+      cok[t] = ww >= 0 && ww < W;
+      roff[t] = min(max(hh, 0), H - 1) * W;
+      coff[t] = min(max(ww, 0), W - 1);
+    }
 #pragma unroll
     for (int ct = 0; ct < CT; ++ct) {
       const T* plane = thin + (n * CT + ct) * HW;
 #pragma unroll
-      for (int r = 0; r < 3; ++r) {
-        const int hh = h + r - 1;
+      for (int r = 0; r < 3; ++r)
+#pragma unroll
+        for (int s = 0; s < 3; ++s) xv[ct * 9 + r * 3 + s] = Store<T>::ld(plane + roff[r] + coff[s]);
+    }
+    float acc[4] = {bs[0], bs[1], bs[2], bs[3]};
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+      for (int r = 0; r < 3; ++r)
 #pragma unroll
         for (int s = 0; s < 3; ++s) {
-          const int ww = w + s - 1;
-          const bool ok = hh >= 0 && hh < H && ww >= 0 && ww < W;
-          const float xv = ok ? Store<T>::ld(plane + (int64_t)hh * W + ww) : 0.0f;
+          const float x = (rok[r] && cok[s]) ? xv[ct * 9 + r * 3 + s] : 0.0f;
 #pragma unroll
-          for (int c = 0; c < 4; ++c) acc[c] = fmaf(xv, wk[c][ct * 9 + r * 3 + s], acc[c]);
+          for (int c = 0; c < 4; ++c) acc[c] = fmaf(x, wk[c][ct * 9 + r * 3 + s], acc[c]);
         }
-      }
-    }
     float o[4];
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
@@ -142,28 +157,36 @@ __global__ __launch_bounds__(NT) void k_thin_out_conv(const T* __restrict__ wide
   float acc[CT];
 #pragma unroll
   for (int ct = 0; ct < CT; ++ct) acc[ct] = bias ? bias[ct] : 0.0f;
+  // channels in groups of 32 elements: the group's loads are issued together (from a
+  // clamped, always valid source pixel), then consumed
+  constexpr int GRP = 32 / V;                  // 16-byte loads per group
   for (int r = 0; r < 3; ++r) {
     const int hh = h + r - 1;
-    if (hh < 0 || hh >= Hc) continue;
+    const bool rok = hh >= 0 && hh < Hc;
+    const int hs = min(max(hh, 0), Hc - 1) >> up;
     for (int s = 0; s < 3; ++s) {
       const int ww = w + s - 1;
-      if (ww < 0 || ww >= Wc) continue;
-      const T* src = wide + ((n * Hin + (hh >> up)) * Win + (ww >> up)) * CW;
+      const float keep = (rok && ww >= 0 && ww < Wc) ? 1.0f : 0.0f;
+      const int ws = min(max(ww, 0), Wc - 1) >> up;
+      const T* src = wide + ((n * Hin + hs) * Win + ws) * CW;
       const float* wt = sw + (r * 3 + s) * CW;
-      for (int c = 0; c < CW; c += V) {
-        float xv[V];
-        Store<T>::ldv(src + c, xv);
+      for (int c0 = 0; c0 < CW; c0 += 32) {
+        float xv[GRP][V];
 #pragma unroll
-        for (int ct = 0; ct < CT; ++ct) {
+        for (int g = 0; g < GRP; ++g) Store<T>::ldv(src + c0 + g * V, xv[g]);
 #pragma unroll
-          for (int j = 0; j < V; j += 4) {
-            const float4 w4 = *reinterpret_cast<const float4*>(wt + ct * 9 * CW + c + j);
-            acc[ct] = fmaf(xv[j], w4.x, acc[ct]);
-            acc[ct] = fmaf(xv[j + 1], w4.y, acc[ct]);
-            acc[ct] = fmaf(xv[j + 2], w4.z, acc[ct]);
-            acc[ct] = fmaf(xv[j + 3], w4.w, acc[ct]);
-          }
-        }
+        for (int g = 0; g < GRP; ++g)
+#pragma unroll
+          for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+            for (int j = 0; j < V; j += 4) {
+              const float4 w4 = *reinterpret_cast<const float4*>(wt + ct * 9 * CW + c0 + g * V + j);
+              float t = xv[g][j] * w4.x;
+              t = fmaf(xv[g][j + 1], w4.y, t);
+              t = fmaf(xv[g][j + 2], w4.z, t);
+              t = fmaf(xv[g][j + 3], w4.w, t);
+              acc[ct] = fmaf(keep, t, acc[ct]);
+            }
       }
     }
   }
@@ -221,12 +244,14 @@ __global__ __launch_bounds__(NT) void k_thin_wgrad(const T* __restrict__ thin, c
         const T* plane = thin + (n * CT + ct) * HWt;
         if (mode == 0) {
           const int hh = ii + r - 1, ww = j + s - 1;
-          if (hh >= 0 && hh < Ht && ww >= 0 && ww < Wt) v = Store<T>::ld(plane + (int64_t)hh * Wt + ww);
+          const float x = Store<T>::ld(plane + (int64_t)min(max(hh, 0), Ht - 1) * Wt + min(max(ww, 0), Wt - 1));
+          v = (hh >= 0 && hh < Ht && ww >= 0 && ww < Wt) ? x : 0.0f;
         } else {
           for (int a = 0; a <= up; ++a)
             for (int b = 0; b <= up; ++b) {
               const int hh = (ii << up) + a - (r - 1), ww = (j << up) + b - (s - 1);
-              if (hh >= 0 && hh < Ht && ww >= 0 && ww < Wt) v += Store<T>::ld(plane + (int64_t)hh * Wt + ww);
+              const float x = Store<T>::ld(plane + (int64_t)min(max(hh, 0), Ht - 1) * Wt + min(max(ww, 0), Wt - 1));
+              v += (hh >= 0 && hh < Ht && ww >= 0 && ww < Wt) ? x : 0.0f;
             }
         }
       }
@@ -296,6 +321,168 @@ __global__ void k_plane_sums(const T* __restrict__ x, int C, int64_t HW, float* 
   if (threadIdx.x == 0) { partial[(n * 2) * C + c] = s1; partial[(n * 2 + 1) * C + c] = s2; }
 }
 
+// ---------------------------------------------------------------------------
+// thin-in conv on the matrix cores (bf16).  A workgroup owns a TH x TW patch of one
+// image (TH*TW = 256 pixels).  The patch plus its halo is copied from the planar
+// input into LDS as interleaved pixels of 4 channels (8 bytes, channel 3 = 0).  For
+// one filter row r the three taps of a pixel are then 12 consecutive bf16 values —
+// one K = 16 MFMA step (the last four weights are zero):
+//   k = 4*s + ci,  A[pixel][k] = tile[h+r][w+s][ci],  B[k][co] = Wk[co][ci][r][s].
+// Three MFMA steps (r = 0,1,2) per 32 pixels x 32 channels; the weights stay in
+// registers for the whole kernel.  Epilogue as in the implicit-GEMM kernel.
+// ---------------------------------------------------------------------------
+typedef __bf16 t_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float t_floatx16 __attribute__((ext_vector_type(16)));
+
+template <int NJ>
+__global__ __launch_bounds__(NT) void k_thin_in_mfma(const bf16_t* __restrict__ thin, const float* __restrict__ wcanon,
+                                                     const float* __restrict__ bias, bf16_t* __restrict__ out,
+                                                     float* __restrict__ partial, int n_img, int H, int W, int CT,
+                                                     int CW, int flip, int act, int TW, int tw_shift) {
+  constexpr int MAXT = (256 / 8 + 2) * (8 + 4) > (4 + 2) * (64 + 4) ? (256 / 8 + 2) * (8 + 4) : (4 + 2) * (64 + 4);
+  __shared__ __attribute__((aligned(16))) bf16_t tile[MAXT * 4];   // [(TH+2)][(TW+4)][4]
+  __shared__ __attribute__((aligned(16))) bf16_t swt[NJ * 32 * 3 * 16];  // [co][r][16]
+  __shared__ float sRed[4][2][NJ * 32];
+  const int TH = NT >> tw_shift;
+  const int PW = TW + 4;                        // padded tile width (col 0 is w0-1)
+  const int tiles_w = (W + TW - 1) / TW, tiles_h = (H + TH - 1) / TH;
+  int b = blockIdx.x;
+  const int tx = b % tiles_w; b /= tiles_w;
+  const int ty = b % tiles_h;
+  const int n = b / tiles_h;
+  const int h0 = ty * TH, w0 = tx * TW;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t HW = (int64_t)H * W;
+
+  // weights -> LDS as bf16 [co][r][k], k = 4*s + ci (zero where ci >= CT or s == 3)
+  for (int i = tid; i < NJ * 32 * 48; i += NT) {
+    const int k = i & 15, r = (i >> 4) % 3, co = i / 48;
+    const int s_ = k >> 2, ci = k & 3;
+    float v = 0.0f;
+    if (co < CW && ci < CT && s_ < 3)
+      v = flip ? wcanon[(((int64_t)ci * CW + co) * 3 + (2 - r)) * 3 + (2 - s_)]
+               : wcanon[(((int64_t)co * CT + ci) * 3 + r) * 3 + s_];
+    swt[i] = f32_to_bf16(v);
+  }
+  // input patch -> LDS, zero outside the image and in the padding channel
+  const int cells = (TH + 2) * PW;
+  for (int i = tid; i < cells * 4; i += NT) {
+    const int ci = i & 3, cell = i >> 2;
+    const int pc = cell % PW, pr = cell / PW;
+    const int hh = h0 + pr - 1, ww = w0 + pc - 1;
+    bf16_t v = 0;
+    if (ci < CT && hh >= 0 && hh < H && ww >= 0 && ww < W) v = thin[((int64_t)n * CT + ci) * HW + (int64_t)hh * W + ww];
+    tile[i] = v;
+  }
+  __syncthreads();
+
+  const int frag_row = lane & 31, g = lane >> 5;
+  t_bf16x8 bfrag[3][NJ];
+#pragma unroll
+  for (int r = 0; r < 3; ++r)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+      bfrag[r][j] = *reinterpret_cast<const t_bf16x8*>(&swt[((j * 32 + frag_row) * 3 + r) * 16 + g * 8]);
+
+  t_floatx16 acc[2][NJ];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int pt = wave * 64 + i * 32 + frag_row;     // this lane's pixel of the patch
+    const int th = pt >> tw_shift, tw = pt & (TW - 1);
+#pragma unroll
+    for (int r = 0; r < 3; ++r) {
+      // k-chunk g: pixels (tw + 2g, tw + 2g + 1) of padded row th + r, 4 channels each = 16 bytes
+      const bf16_t* src = &tile[((th + r) * PW + tw + 2 * g) * 4];
+      union { uint2 u[2]; t_bf16x8 v; } a;
+      a.u[0] = *reinterpret_cast<const uint2*>(src);
+      a.u[1] = *reinterpret_cast<const uint2*>(src + 4);
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, bfrag[r][j], acc[i][j], 0, 0, 0);
+    }
+  }
+
+  // epilogue: element e of lane l in tile (i,j): patch pixel wave*64 + i*32 + (e/4)*8 + (l/32)*4 + e%4, channel j*32 + l%32
+  const int col_lane = lane & 31, row_lane = (lane >> 5) * 4;
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int col = j * 32 + col_lane;
+    const bool col_ok = col < CW;
+    const float bs = (bias && col_ok) ? bias[col] : 0.0f;
+    float s1 = 0.0f, s2 = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int pt = wave * 64 + i * 32 + (e >> 2) * 8 + row_lane + (e & 3);
+        const int hh = h0 + (pt >> tw_shift), ww = w0 + (pt & (TW - 1));
+        if (col_ok && hh < H && ww < W) {
+          const float v = bf16_to_f32(f32_to_bf16(acc[i][j][e] + bs));
+          s1 += v;
+          s2 = fmaf(v, v, s2);
+          out[(((int64_t)n * H + hh) * W + ww) * CW + col] = f32_to_bf16(apply_act(v, act));
+        }
+      }
+    }
+    if (partial) {
+      s1 += __shfl_xor(s1, 32, 64);
+      s2 += __shfl_xor(s2, 32, 64);
+      if (lane < 32) { sRed[wave][0][col] = s1; sRed[wave][1][col] = s2; }
+    }
+  }
+  if (partial) {
+    __syncthreads();
+    for (int i = tid; i < 2 * NJ * 32; i += NT) {
+      const int q = i / (NJ * 32), c = i % (NJ * 32);
+      if (c < CW) partial[((int64_t)blockIdx.x * 2 + q) * CW + c] = sRed[0][q][c] + sRed[1][q][c] + sRed[2][q][c] + sRed[3][q][c];
+    }
+  }
+}
+
+struct ThinTile { int tw, shift, blocks; };
+ThinTile thin_tile(int n, int h, int w) {
+  int tw = 8, shift = 3;
+  while (tw < 64 && tw < w) { tw <<= 1; ++shift; }
+  const int th = NT / tw;
+  ThinTile t;
+  t.tw = tw; t.shift = shift;
+  t.blocks = n * ((h + th - 1) / th) * ((w + tw - 1) / tw);
+  return t;
+}
+
+}  // namespace
+
+bool thin_in_mfma_supported(int ct, int cw, int k, int up, int dtype) {
+  return dtype == AE_BF16 && k == 3 && !up && ct >= 1 && ct <= 4 && cw % 32 == 0 && cw <= 128;
+}
+
+int thin_in_mfma_blocks(int n, int h, int w) { return thin_tile(n, h, w).blocks; }
+
+int launch_thin_in_mfma(const void* thin, const float* wcanon, const float* bias, void* out, float* partial, int n,
+                        int h, int w, int ct, int cw, int flip, int act, hipStream_t s) {
+  if (!thin_in_mfma_supported(ct, cw, 3, 0, AE_BF16)) return fail(AE_EINVAL, "thin_in_mfma: shape not supported");
+  const ThinTile t = thin_tile(n, h, w);
+  const int nj = cw / 32;
+#define LAUNCH_TIM(NJV)                                                                                          \
+  hipLaunchKernelGGL((k_thin_in_mfma<NJV>), dim3((unsigned)t.blocks), dim3(NT), 0, s, (const bf16_t*)thin, wcanon, \
+                     bias, (bf16_t*)out, partial, n, h, w, ct, cw, flip, act, t.tw, t.shift)
+  switch (nj) {
+    case 1: LAUNCH_TIM(1); break;
+    case 2: LAUNCH_TIM(2); break;
+    case 3: LAUNCH_TIM(3); break;
+    default: LAUNCH_TIM(4); break;
+  }
+#undef LAUNCH_TIM
+  return launch_status("thin_in_mfma");
+}
+
+namespace {
 }  // namespace
 
 bool thin_in_supported(int ct, int cw, int k, int up) {
@@ -306,8 +493,8 @@ bool thin_in_supported(int ct, int cw, int k, int up) {
 }
 
 bool thin_out_supported(int ct, int cw, int k, int dtype) {
-  const int v = dtype == AE_BF16 ? 8 : 4;
-  return k == 3 && ct >= 1 && ct <= 4 && cw % v == 0 && (int64_t)ct * 9 * cw * 4 <= 60 * 1024;
+  (void)dtype;
+  return k == 3 && ct >= 1 && ct <= 4 && cw % 32 == 0 && (int64_t)ct * 9 * cw * 4 <= 60 * 1024;
 }
 
 int thin_in_partial_rows() { return THIN_ROWS; }

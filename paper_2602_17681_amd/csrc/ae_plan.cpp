@@ -259,6 +259,7 @@ int build_plan(const char* spec, int batch, int dtype, int bn_mode, Plan* plan) 
       st.off_wpack_d = take(wel * es);
       if (st.has_bn) st.off_bn = take(6 * (int64_t)st.cout * 4);
       int64_t blocks = std::max<int64_t>((rows + 127) / 128, reduce_blocks(rows));  // finest partial-sum granularity
+      if (st.thin == 1) blocks = std::max<int64_t>(blocks, thin_in_mfma_blocks(batch, st.hc, st.wc));
       plan->max_partial_floats = std::max(plan->max_partial_floats, blocks * 2 * std::max(st.cout, st.cin));
       WgradArgs wa;
       wa.x = wa.dy = nullptr; wa.dw_canonical = nullptr;
