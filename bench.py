@@ -139,6 +139,10 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="cfg5", choices=sorted(wl.CONFIGS))
+    ap.add_argument("--spec", default=None, help="benchmark an arbitrary layer spec instead of a named configuration")
+    ap.add_argument("--batch", type=int, default=32)
+    ap.add_argument("--dtype", default="bf16", choices=["f32", "bf16"])
+    ap.add_argument("--forward-only", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-per-config", action="store_true")
     ap.add_argument("--kernels", action="store_true", help="also print the per-kernel table to stderr")
@@ -152,6 +156,12 @@ def main():
     from paper_2602_17681_amd import binding as ae
 
     name = args.config
+    if args.spec:
+        name = "custom"
+        wl.CONFIGS[name] = dict(spec=args.spec, batch=args.batch, dtype=args.dtype, seed=7, snr_db=[10.0],
+                                backward=not args.forward_only)
+        args.no_per_config = True
+        args.no_cpu_baseline = True
     cfg = wl.CONFIGS[name]
     st = build_case(name, torch, ae)
     # timed region: exactly `steps` steps, per-kernel HIP events recorded on the same stream

@@ -29,25 +29,43 @@ struct IgemmParams {
   int Hc, Wc, Cin, ksz, up;
   int act;
   int tiles_n;
+  unsigned x_bytes, w_bytes;   // sizes of the two operand tensors (buffer range checks)
 };
 
 // ---------------------------------------------------------------------------
-// bf16 kernel.  BK = 32 elements: a slab row is 64 bytes = four 16-byte chunks.  LDS
-// rows are not padded; chunk c of row r is stored in slot c ^ ((r >> 1) & 3), which
-// makes both the 16-byte stores of the loader and the 16-byte fragment reads of the
-// MFMA operands conflict-free.  Global loads run two slabs ahead of the MFMAs through
-// two register sets; LDS is double buffered, one barrier per slab.
+// bf16 kernel.  A slab is BK = 32 or 64 elements of K: a slab row is 64 or 128 bytes =
+// CPR 16-byte chunks.  LDS rows are not padded; chunk c of row r is stored in slot
+// c ^ f(r) with f(r) = (r>>2)&3 (BK 32) or (r>>1)&7 (BK 64): the LDS has 64 banks and
+// serves 16 lanes of a 16-byte access per pass, and with this swizzle the 16 rows of a
+// pass fall into 16 different 16-byte columns for the loader's stores and for the MFMA
+// fragment reads alike.  Global loads are buffer loads: the hardware range check returns
+// zero for the offsets that the loader marks invalid (zero padding of the image, rows
+// past M or N), so no select or clamp is needed, and addresses are 32-bit offsets that
+// only change when the filter tap changes.  Loads run two slabs ahead of the MFMAs
+// through two register sets; LDS is double buffered, one barrier per slab.
 // ---------------------------------------------------------------------------
-template <int BM, int BN, int WGM, int WGN>
+typedef unsigned uint4v __attribute__((ext_vector_type(4)));
+constexpr unsigned kOob = 0x80000000u;         // beyond any tensor (tensors are < 2 GiB): reads as zero
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+
+template <int BM, int BN, int WGM, int WGN, int BK>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k_igemm_bf16(IgemmParams p) {
   static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
-  constexpr int BK = 32;
+  static_assert(BK == 32 || BK == 64, "slab depth");
+  constexpr int CPR = BK / 8;                   // 16-byte chunks per slab row
+  constexpr int RSTEP = 256 / CPR;              // rows covered by one pass of the 256 loader threads
   constexpr int WM = BM / WGM, WN = BN / WGN;   // wave tile
   constexpr int MI = WM / 32, NJ = WN / 32;     // 32x32 MFMA tiles per wave
-  constexpr int A_CHUNKS = BM * 4 / 256;        // 16-byte chunks per thread per slab
-  constexpr int B_CHUNKS = BN * 4 / 256;
-  __shared__ __attribute__((aligned(16))) bf16_t sA[2][BM * BK];
-  __shared__ __attribute__((aligned(16))) bf16_t sB[2][BN * BK];
+  constexpr int A_CHUNKS = BM / RSTEP, B_CHUNKS = BN / RSTEP;
+  constexpr int SW = WN + 8;                    // staging row stride of the epilogue (elements)
+  constexpr int SLAB_ELEMS = 2 * (BM + BN) * BK;
+  constexpr int STAGE_ELEMS = 4 * 32 * SW;
+  __shared__ __attribute__((aligned(16))) bf16_t smem[SLAB_ELEMS > STAGE_ELEMS ? SLAB_ELEMS : STAGE_ELEMS];
+  bf16_t* const sA = smem;                      // [2][BM*BK]
+  bf16_t* const sB = smem + 2 * BM * BK;        // [2][BN*BK]
   __shared__ float sRed[WGM][2][BN];            // [wave row][sum | sumsq][column]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -56,85 +74,83 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   const int64_t tile_m = blockIdx.x / p.tiles_n;
   const int64_t m0 = tile_m * BM;
   const int n0 = tile_n * BN;
-  const bf16_t* __restrict__ X = (const bf16_t*)p.x;
-  const bf16_t* __restrict__ W = (const bf16_t*)p.w;
   const int pad = (p.ksz - 1) >> 1;
   const int Hin = p.Hc >> p.up, Win = p.Wc >> p.up;
+  const __amdgpu_buffer_rsrc_t rX = make_rsrc(p.x, p.x_bytes);
+  const __amdgpu_buffer_rsrc_t rW = make_rsrc(p.w, p.w_bytes);
 
-  // --- loader bookkeeping: thread t moves rows (t>>2) + 64*i, LDS slot t&3 of each
-  const int slot = tid & 3;
-  const int lrow = tid >> 2;
-  const int gchunk = slot ^ ((lrow >> 1) & 3);  // 64*i keeps (row>>1)&3: the same global chunk for every i
+  // --- loader bookkeeping: thread t moves rows (t / CPR) + RSTEP*i, LDS slot t % CPR of each
+  const int slot = tid % CPR;
+  const int lrow = tid / CPR;
+  const int fsw = BK == 32 ? ((lrow >> 2) & 3) : ((lrow >> 1) & 7);   // RSTEP*i does not touch these bits
+  const int gchunk = slot ^ fsw;
   int a_h[A_CHUNKS], a_w[A_CHUNKS];
-  int64_t a_img[A_CHUNKS];                      // element offset of the sample's image
-  bool a_ok[A_CHUNKS];                          // row below M
+  unsigned a_img[A_CHUNKS];                     // byte offset of the sample's image, kOob if the row is past M
+  unsigned a_off[A_CHUNKS];                     // byte offset of the current tap's pixel (+ chunk), kOob if padding
 #pragma unroll
   for (int i = 0; i < A_CHUNKS; ++i) {
-    const int64_t m = m0 + lrow + i * 64;
-    a_ok[i] = m < p.M;
-    const unsigned mu = a_ok[i] ? (unsigned)m : 0u;
+    const int64_t m = m0 + lrow + i * RSTEP;
+    const bool ok = m < p.M;
+    const unsigned mu = ok ? (unsigned)m : 0u;
     a_w[i] = (int)(mu % (unsigned)p.Wc);
     const unsigned t = mu / (unsigned)p.Wc;
     a_h[i] = (int)(t % (unsigned)p.Hc);
-    a_img[i] = (int64_t)(t / (unsigned)p.Hc) * Hin * Win * p.Cin;
+    a_img[i] = ok ? (t / (unsigned)p.Hc) * (unsigned)(Hin * Win) * (unsigned)p.Cin * 2u : kOob;
   }
-  // rows past N read the last valid weight row and are zeroed in registers
-  const bf16_t* b_ptr[B_CHUNKS];
-  bool b_ok[B_CHUNKS];
+  unsigned b_off[B_CHUNKS];
 #pragma unroll
   for (int i = 0; i < B_CHUNKS; ++i) {
-    const int row = n0 + lrow + i * 64;
-    b_ok[i] = row < p.N;
-    b_ptr[i] = W + (int64_t)(b_ok[i] ? row : p.N - 1) * p.K + gchunk * 8;
+    const int row = n0 + lrow + i * RSTEP;
+    b_off[i] = row < p.N ? (unsigned)row * (unsigned)p.K * 2u + (unsigned)gchunk * 16u : kOob;
   }
 
   int rs = 0, ci0 = 0;                          // filter tap and first channel of the next slab to load
-  int kload = 0;                                // index of the next slab to load
-
-  // Every load goes to a valid address (coordinates clamped into the image); what the
-  // zero padding or the ragged edges require is then zeroed in registers.
-#define IGEMM_LOAD(RA, RB)                                                                                   \
+  unsigned kbyte = 0;                           // byte offset of the next slab inside a weight row
+#define IGEMM_TAP()                                                                                          \
   {                                                                                                          \
     const int r_ = rs / p.ksz, s_ = rs - r_ * p.ksz;                                                         \
     _Pragma("unroll") for (int i = 0; i < A_CHUNKS; ++i) {                                                   \
       const int hh = a_h[i] + r_ - pad, ww = a_w[i] + s_ - pad;                                              \
-      const bool ok = a_ok[i] && hh >= 0 && hh < p.Hc && ww >= 0 && ww < p.Wc;                               \
-      const int hc_ = min(max(hh, 0), p.Hc - 1), wc_ = min(max(ww, 0), p.Wc - 1);                            \
-      uint4 v = *reinterpret_cast<const uint4*>(X + a_img[i] +                                               \
-                                                ((int64_t)(hc_ >> p.up) * Win + (wc_ >> p.up)) * p.Cin + ci0 + \
-                                                gchunk * 8);                                                 \
-      if (!ok) { v.x = 0u; v.y = 0u; v.z = 0u; v.w = 0u; }                                                   \
-      RA[i] = v;                                                                                             \
+      const bool ok = hh >= 0 && hh < p.Hc && ww >= 0 && ww < p.Wc;                                          \
+      const unsigned pix = (unsigned)((hh >> p.up) * Win + (ww >> p.up));                                    \
+      a_off[i] = ok ? (a_img[i] | 0u) + pix * (unsigned)p.Cin * 2u + (unsigned)gchunk * 16u : kOob;          \
+      if (a_img[i] == kOob) a_off[i] = kOob;                                                                 \
     }                                                                                                        \
-    _Pragma("unroll") for (int i = 0; i < B_CHUNKS; ++i) {                                                   \
-      uint4 v = *reinterpret_cast<const uint4*>(b_ptr[i] + (int64_t)kload * BK);                             \
-      if (!b_ok[i]) { v.x = 0u; v.y = 0u; v.z = 0u; v.w = 0u; }                                              \
-      RB[i] = v;                                                                                             \
-    }                                                                                                        \
-    ci0 += BK;                                                                                               \
-    if (ci0 == p.Cin) { ci0 = 0; ++rs; }                                                                     \
-    ++kload;                                                                                                 \
   }
+#define IGEMM_LOAD(RA, RB)                                                                                   \
+  {                                                                                                          \
+    if (ci0 == 0) IGEMM_TAP();                                                                               \
+    _Pragma("unroll") for (int i = 0; i < A_CHUNKS; ++i)                                                     \
+        RA[i] = __builtin_amdgcn_raw_buffer_load_b128(rX, a_off[i] + (unsigned)ci0 * 2u, 0, 0);              \
+    _Pragma("unroll") for (int i = 0; i < B_CHUNKS; ++i)                                                     \
+        RB[i] = __builtin_amdgcn_raw_buffer_load_b128(rW, b_off[i] + kbyte, 0, 0);                           \
+    ci0 += BK;                                                                                               \
+    kbyte += BK * 2;                                                                                         \
+    if (ci0 == p.Cin) { ci0 = 0; ++rs; }                                                                     \
+  }
+  const int st_off = lrow * BK + slot * 8;      // this thread's element offset inside a slab buffer (+ i*RSTEP*BK)
 #define IGEMM_STORE(BUF, RA, RB)                                                                             \
   {                                                                                                          \
     _Pragma("unroll") for (int i = 0; i < A_CHUNKS; ++i)                                                     \
-        *reinterpret_cast<uint4*>(&sA[BUF][(lrow + i * 64) * BK + slot * 8]) = RA[i];                        \
+        *reinterpret_cast<uint4v*>(&sA[(BUF) * BM * BK + st_off + i * RSTEP * BK]) = RA[i];                  \
     _Pragma("unroll") for (int i = 0; i < B_CHUNKS; ++i)                                                     \
-        *reinterpret_cast<uint4*>(&sB[BUF][(lrow + i * 64) * BK + slot * 8]) = RB[i];                        \
+        *reinterpret_cast<uint4v*>(&sB[(BUF) * BN * BK + st_off + i * RSTEP * BK]) = RB[i];                  \
   }
-  // fragment of row r, k-chunk c (of 4): slot c ^ ((r>>1)&3)
+  // fragment reads: lane l wants row (l%32) of a 32-row MFMA tile, k-chunk 2*ks + l/32;
+  // the lane-dependent part of the address is the same for A and B and for every tile
+  const int frag_row = lane & 31, frag_c = lane >> 5;
+  const int ffr = BK == 32 ? ((frag_row >> 2) & 3) : ((frag_row >> 1) & 7);
+  int lane_off[BK / 16];
+#pragma unroll
+  for (int ks = 0; ks < BK / 16; ++ks) lane_off[ks] = frag_row * BK + (((ks * 2 + frag_c) ^ ffr) * 8);
 #define IGEMM_COMPUTE(BUF)                                                                                   \
   {                                                                                                          \
     _Pragma("unroll") for (int ks = 0; ks < BK / 16; ++ks) {                                                 \
       bf16x8 a[MI], b[NJ];                                                                                   \
-      _Pragma("unroll") for (int i = 0; i < MI; ++i) {                                                       \
-        const int r = wm * WM + i * 32 + frag_row;                                                           \
-        a[i] = *reinterpret_cast<const bf16x8*>(&sA[BUF][r * BK + (((ks * 2 + frag_c) ^ ((r >> 1) & 3)) * 8)]); \
-      }                                                                                                      \
-      _Pragma("unroll") for (int j = 0; j < NJ; ++j) {                                                       \
-        const int r = wn * WN + j * 32 + frag_row;                                                           \
-        b[j] = *reinterpret_cast<const bf16x8*>(&sB[BUF][r * BK + (((ks * 2 + frag_c) ^ ((r >> 1) & 3)) * 8)]); \
-      }                                                                                                      \
+      _Pragma("unroll") for (int i = 0; i < MI; ++i)                                                         \
+          a[i] = *reinterpret_cast<const bf16x8*>(&sA[(BUF) * BM * BK + (wm * WM + i * 32) * BK + lane_off[ks]]); \
+      _Pragma("unroll") for (int j = 0; j < NJ; ++j)                                                         \
+          b[j] = *reinterpret_cast<const bf16x8*>(&sB[(BUF) * BN * BK + (wn * WN + j * 32) * BK + lane_off[ks]]); \
       _Pragma("unroll") for (int i = 0; i < MI; ++i)                                                         \
         _Pragma("unroll") for (int j = 0; j < NJ; ++j)                                                       \
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);             \
@@ -150,8 +166,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
   const int KT = p.K / BK;
-  const int frag_row = lane & 31, frag_c = lane >> 5;
-  uint4 ra0[A_CHUNKS], rb0[B_CHUNKS], ra1[A_CHUNKS], rb1[B_CHUNKS];
+  uint4v ra0[A_CHUNKS], rb0[B_CHUNKS], ra1[A_CHUNKS], rb1[B_CHUNKS];
   IGEMM_LOAD(ra0, rb0);
   if (KT > 1) IGEMM_LOAD(ra1, rb1);
   IGEMM_STORE(0, ra0, rb0);
@@ -169,41 +184,66 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
     if (kt + 2 < KT) IGEMM_STORE(0, ra0, rb0);
     __syncthreads();
   }
+#undef IGEMM_TAP
 #undef IGEMM_LOAD
 #undef IGEMM_STORE
 #undef IGEMM_COMPUTE
 
   // --- epilogue.  Accumulator element e of lane l in tile (i,j):
   //     row = wm*WM + i*32 + (e/4)*8 + (l/32)*4 + e%4,  column = wn*WN + j*32 + l%32
+  // Results go through a wave-private LDS staging area (the slab buffers are free now:
+  // the K loop ended on a barrier) so that global stores are 16 bytes wide and each
+  // instruction covers whole 2*WN-byte row segments.
   bf16_t* __restrict__ Y = (bf16_t*)p.y;
   const int col_lane = lane & 31, row_lane = (lane >> 5) * 4;
+  const bool wide_store = (p.N % 8 == 0) && !p.y_aux;
+  bf16_t* stage = smem + wave * (32 * SW);
+  float s1[NJ], s2[NJ];
 #pragma unroll
-  for (int j = 0; j < NJ; ++j) {
-    const int col = n0 + wn * WN + j * 32 + col_lane;
-    const bool col_ok = col < p.N;
-    const float bias = (p.bias && col_ok) ? p.bias[col] : 0.0f;
-    float s1 = 0.0f, s2 = 0.0f;
+  for (int j = 0; j < NJ; ++j) { s1[j] = 0.0f; s2[j] = 0.0f; }
 #pragma unroll
-    for (int i = 0; i < MI; ++i) {
+  for (int i = 0; i < MI; ++i) {
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      const int col = n0 + wn * WN + j * 32 + col_lane;
+      const bool col_ok = col < p.N;
+      const float bias = (p.bias && col_ok) ? p.bias[col] : 0.0f;
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const int64_t m = m0 + wm * WM + i * 32 + (e >> 2) * 8 + row_lane + (e & 3);
-        if (m < p.M && col_ok) {
-          const float v = bf16_to_f32(f32_to_bf16(acc[i][j][e] + bias));   // the stored conv result
-          s1 += v;
-          s2 = fmaf(v, v, s2);
-          const float a = apply_act(v, p.act);
+        const int lr = (e >> 2) * 8 + row_lane + (e & 3);
+        const int64_t m = m0 + wm * WM + i * 32 + lr;
+        const float v = bf16_to_f32(f32_to_bf16(acc[i][j][e] + bias));   // the stored conv result
+        if (m < p.M && col_ok) { s1[j] += v; s2[j] = fmaf(v, v, s2[j]); }
+        const float a = apply_act(v, p.act);
+        if (wide_store) {
+          stage[lr * SW + j * 32 + col_lane] = f32_to_bf16(a);
+        } else if (m < p.M && col_ok) {
           Y[m * p.N + col] = f32_to_bf16(a);
           if (p.y_aux) p.y_aux[m * p.N + col] = a;
         }
       }
     }
-    if (p.partial) {
-      s1 += __shfl_xor(s1, 32, 64);
-      s2 += __shfl_xor(s2, 32, 64);
+    if (wide_store) {
+      constexpr int CPR = WN / 8;                // 16-byte chunks per row
+#pragma unroll
+      for (int c = 0; c < (32 * CPR) / 64; ++c) {
+        const int idx = c * 64 + lane;
+        const int lr = idx / CPR, ch = idx % CPR;
+        const int64_t m = m0 + wm * WM + i * 32 + lr;
+        const int col0 = n0 + wn * WN + ch * 8;
+        if (m < p.M && col0 < p.N)
+          *reinterpret_cast<uint4*>(Y + m * p.N + col0) = *reinterpret_cast<const uint4*>(&stage[lr * SW + ch * 8]);
+      }
+    }
+  }
+  if (p.partial) {
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      float t1 = s1[j] + __shfl_xor(s1[j], 32, 64);
+      float t2 = s2[j] + __shfl_xor(s2[j], 32, 64);
       if (lane < 32) {
-        sRed[wm][0][wn * WN + j * 32 + col_lane] = s1;
-        sRed[wm][1][wn * WN + j * 32 + col_lane] = s2;
+        sRed[wm][0][wn * WN + j * 32 + col_lane] = t1;
+        sRed[wm][1][wn * WN + j * 32 + col_lane] = t2;
       }
     }
   }
@@ -219,15 +259,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   }
 }
 
-struct IgemmTile { int bm, bn; };
+struct IgemmTile { int bm, bn, bk; };
 
 // Largest tile that still gives every compute unit about two workgroups.
-IgemmTile pick_tile(int64_t M, int cout) {
+IgemmTile pick_tile(int64_t M, int cout, int cin) {
   const int bn = cout > 64 ? 128 : 64;
   const int64_t tiles_n = (cout + bn - 1) / bn;
-  int bm = bn == 64 ? 256 : 128;               // 256x128 does not fit the register budget of two waves per SIMD
+  int bm = bn == 64 ? 256 : 128;
   if (((M + 255) / 256) * tiles_n < 512) bm = 128;
-  return IgemmTile{bm, bn};
+  int bk = cin % 64 == 0 ? 64 : 32;
+  if (bm == 256) bk = 32;                       // 256x64 with 64-deep slabs exceeds the register / LDS budget of two waves per SIMD
+  return IgemmTile{bm, bn, bk};
 }
 
 }  // namespace
@@ -236,12 +278,15 @@ bool conv_mfma_supported(const ConvArgs& a) {
   if (a.dtype != AE_BF16) return false;
   if (a.cin % 32 != 0 || a.cout < 32) return false;
   const int64_t M = (int64_t)a.n * a.hc * a.wc;
+  const int64_t x_bytes = (int64_t)a.n * (a.hc >> a.up) * (a.wc >> a.up) * a.cin * 2;
+  const int64_t w_bytes = (int64_t)a.cout * a.k * a.k * a.cin * 2;
+  if (x_bytes >= 0x7FFFFFFF || w_bytes >= 0x7FFFFFFF) return false;   // 32-bit buffer offsets
   return M * ((a.cout + 63) / 64) / 128 < 0x7FFFFFFF && M < 0x7FFFFFFF;
 }
 
 int conv_partial_rows(const ConvArgs& a, bool mfma) {
   if (!mfma) return kReduceRows;
-  return pick_tile((int64_t)a.n * a.hc * a.wc, a.cout).bm;
+  return pick_tile((int64_t)a.n * a.hc * a.wc, a.cout, a.cin).bm;
 }
 
 int launch_conv_mfma(const ConvArgs& a, hipStream_t s) {
@@ -251,14 +296,21 @@ int launch_conv_mfma(const ConvArgs& a, hipStream_t s) {
   p.M = (int64_t)a.n * a.hc * a.wc;
   p.N = a.cout; p.K = a.k * a.k * a.cin;
   p.Hc = a.hc; p.Wc = a.wc; p.Cin = a.cin; p.ksz = a.k; p.up = a.up; p.act = a.act;
-  const IgemmTile t = pick_tile(p.M, a.cout);
+  p.x_bytes = (unsigned)((int64_t)a.n * (a.hc >> a.up) * (a.wc >> a.up) * a.cin * 2);
+  p.w_bytes = (unsigned)((int64_t)a.cout * a.k * a.k * a.cin * 2);
+  const IgemmTile t = pick_tile(p.M, a.cout, a.cin);
   p.tiles_n = (a.cout + t.bn - 1) / t.bn;
   const int64_t tiles_m = (p.M + t.bm - 1) / t.bm;
   dim3 grid((unsigned)(tiles_m * p.tiles_n));
-  if (t.bm == 256 && t.bn == 128) hipLaunchKernelGGL((k_igemm_bf16<256, 128, 2, 2>), grid, dim3(256), 0, s, p);
-  else if (t.bm == 256) hipLaunchKernelGGL((k_igemm_bf16<256, 64, 4, 1>), grid, dim3(256), 0, s, p);
-  else if (t.bn == 128) hipLaunchKernelGGL((k_igemm_bf16<128, 128, 2, 2>), grid, dim3(256), 0, s, p);
-  else hipLaunchKernelGGL((k_igemm_bf16<128, 64, 2, 2>), grid, dim3(256), 0, s, p);
+#define IGEMM_LAUNCH(BMV, BNV, GM, GN)                                                              \
+  do {                                                                                              \
+    if (t.bk == 64) hipLaunchKernelGGL((k_igemm_bf16<BMV, BNV, GM, GN, 64>), grid, dim3(256), 0, s, p); \
+    else hipLaunchKernelGGL((k_igemm_bf16<BMV, BNV, GM, GN, 32>), grid, dim3(256), 0, s, p);        \
+  } while (0)
+  if (t.bm == 256) IGEMM_LAUNCH(256, 64, 4, 1);
+  else if (t.bn == 128) IGEMM_LAUNCH(128, 128, 2, 2);
+  else IGEMM_LAUNCH(128, 64, 2, 2);
+#undef IGEMM_LAUNCH
   return launch_status("conv_mfma");
 }
 

@@ -408,32 +408,50 @@ __global__ __launch_bounds__(NT) void k_thin_in_mfma(const bf16_t* __restrict__ 
     }
   }
 
-  // epilogue: element e of lane l in tile (i,j): patch pixel wave*64 + i*32 + (e/4)*8 + (l/32)*4 + e%4, channel j*32 + l%32
+  // epilogue: element e of lane l in tile (i,j): patch pixel wave*64 + i*32 + (e/4)*8 + (l/32)*4 + e%4,
+  // channel j*32 + l%32.  Staged through wave-private LDS so that global stores are 16 bytes wide.
+  constexpr int SW = NJ * 32 + 8;
+  __shared__ __attribute__((aligned(16))) bf16_t stage_all[4 * 32 * SW];
+  bf16_t* stage = stage_all + wave * (32 * SW);
   const int col_lane = lane & 31, row_lane = (lane >> 5) * 4;
+  float s1[NJ], s2[NJ];
 #pragma unroll
-  for (int j = 0; j < NJ; ++j) {
-    const int col = j * 32 + col_lane;
-    const bool col_ok = col < CW;
-    const float bs = (bias && col_ok) ? bias[col] : 0.0f;
-    float s1 = 0.0f, s2 = 0.0f;
+  for (int j = 0; j < NJ; ++j) { s1[j] = 0.0f; s2[j] = 0.0f; }
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+  for (int i = 0; i < 2; ++i) {
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      const int col = j * 32 + col_lane;
+      const bool col_ok = col < CW;
+      const float bs = (bias && col_ok) ? bias[col] : 0.0f;
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const int pt = wave * 64 + i * 32 + (e >> 2) * 8 + row_lane + (e & 3);
+        const int lr = (e >> 2) * 8 + row_lane + (e & 3);
+        const int pt = wave * 64 + i * 32 + lr;
         const int hh = h0 + (pt >> tw_shift), ww = w0 + (pt & (TW - 1));
-        if (col_ok && hh < H && ww < W) {
-          const float v = bf16_to_f32(f32_to_bf16(acc[i][j][e] + bs));
-          s1 += v;
-          s2 = fmaf(v, v, s2);
-          out[(((int64_t)n * H + hh) * W + ww) * CW + col] = f32_to_bf16(apply_act(v, act));
-        }
+        const float v = bf16_to_f32(f32_to_bf16(acc[i][j][e] + bs));
+        if (col_ok && hh < H && ww < W) { s1[j] += v; s2[j] = fmaf(v, v, s2[j]); }
+        stage[lr * SW + col] = f32_to_bf16(apply_act(v, act));
       }
     }
-    if (partial) {
-      s1 += __shfl_xor(s1, 32, 64);
-      s2 += __shfl_xor(s2, 32, 64);
-      if (lane < 32) { sRed[wave][0][col] = s1; sRed[wave][1][col] = s2; }
+    constexpr int CPR = NJ * 4;                  // 16-byte chunks per pixel row
+#pragma unroll
+    for (int c = 0; c < (32 * CPR) / 64; ++c) {
+      const int idx = c * 64 + lane;
+      const int lr = idx / CPR, ch = idx % CPR;
+      const int pt = wave * 64 + i * 32 + lr;
+      const int hh = h0 + (pt >> tw_shift), ww = w0 + (pt & (TW - 1));
+      if (hh < H && ww < W && ch * 8 < CW)
+        *reinterpret_cast<uint4*>(out + (((int64_t)n * H + hh) * W + ww) * CW + ch * 8) =
+            *reinterpret_cast<const uint4*>(&stage[lr * SW + ch * 8]);
+    }
+  }
+  if (partial) {
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      const float t1 = s1[j] + __shfl_xor(s1[j], 32, 64);
+      const float t2 = s2[j] + __shfl_xor(s2[j], 32, 64);
+      if (lane < 32) { sRed[wave][0][j * 32 + col_lane] = t1; sRed[wave][1][j * 32 + col_lane] = t2; }
     }
   }
   if (partial) {
