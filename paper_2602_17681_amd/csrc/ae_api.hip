@@ -113,8 +113,8 @@ int forward_conv(ae_model* m, int si, Step& st, const float* params, const void*
   const void* w = nullptr;
   if (st.thin == 1) {
     // canonical weights are read directly
-  } else if (st.k == 1 && P.dtype == AE_F32) {
-    w = params + st.w_off;  // [C_out][C_in] is already the packed order
+  } else if (st.k == 1 && P.dtype == AE_F32 && !st.mfma) {
+    w = params + st.w_off;  // [C_out][C_in] is already the packed order (the MFMA loader wants a 16-byte aligned copy)
   } else {
     TIMED(si, "fwd.pack_weights", 0.0, wel * (4.0 + es),
           launch_pack_weights(params + st.w_off, st.wpack, st.cout, st.cin, st.k, P.dtype, false, s));

@@ -33,39 +33,59 @@ struct IgemmParams {
 };
 
 // ---------------------------------------------------------------------------
-// bf16 kernel.  A slab is BK = 32 or 64 elements of K: a slab row is 64 or 128 bytes =
-// CPR 16-byte chunks.  LDS rows are not padded; chunk c of row r is stored in slot
-// c ^ f(r) with f(r) = (r>>2)&3 (BK 32) or (r>>1)&7 (BK 64): the LDS has 64 banks and
-// serves 16 lanes of a 16-byte access per pass, and with this swizzle the 16 rows of a
-// pass fall into 16 different 16-byte columns for the loader's stores and for the MFMA
-// fragment reads alike.  Global loads are buffer loads: the hardware range check returns
-// zero for the offsets that the loader marks invalid (zero padding of the image, rows
-// past M or N), so no select or clamp is needed, and addresses are 32-bit offsets that
-// only change when the filter tap changes.  Loads run two slabs ahead of the MFMAs
-// through two register sets; LDS is double buffered, one barrier per slab.
+// The kernel, for T = bf16 (v_mfma_f32_32x32x16_bf16) or T = float (v_mfma_f32_32x32x2_f32).
+// A slab row is BKB = 64 or 128 bytes of K = CPR 16-byte chunks.  LDS rows are not
+// padded; chunk c of row r is stored in slot c ^ f(r) with f(r) = (r>>2)&3 (64-byte rows)
+// or (r>>1)&7 (128-byte rows): the LDS has 64 banks and serves 16 lanes of a 16-byte
+// access per pass, and with this swizzle the 16 rows of a pass fall into 16 different
+// 16-byte columns for the loader's stores and for the MFMA fragment reads alike.
+// A fragment read fetches 16 bytes per lane: lanes 0-31 chunk 2*ks, lanes 32-63 chunk
+// 2*ks+1 of their row.  For bf16 that is exactly the operand of one K=16 MFMA; for fp32
+// the four floats feed four K=2 MFMAs (component j of the low lanes is paired with
+// component j of the high lanes — any pairing works as long as A and B use the same).
+// Global loads are buffer loads: the hardware range check returns zero for the offsets
+// that the loader marks invalid (zero padding of the image, rows past M or N), so no
+// select or clamp is needed, and addresses are 32-bit byte offsets that only change when
+// the filter tap changes.  Loads run two slabs ahead of the MFMAs through two register
+// sets; LDS is double buffered, one barrier per slab.
 // ---------------------------------------------------------------------------
 typedef unsigned uint4v __attribute__((ext_vector_type(4)));
+typedef float float4v __attribute__((ext_vector_type(4)));
 constexpr unsigned kOob = 0x80000000u;         // beyond any tensor (tensors are < 2 GiB): reads as zero
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
 }
 
-template <int BM, int BN, int WGM, int WGN, int BK>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k_igemm_bf16(IgemmParams p) {
+template <typename T> __device__ __forceinline__ void mma_step(const uint4v& a, const uint4v& b, floatx16& c);
+template <> __device__ __forceinline__ void mma_step<bf16_t>(const uint4v& a, const uint4v& b, floatx16& c) {
+  c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+template <> __device__ __forceinline__ void mma_step<float>(const uint4v& a, const uint4v& b, floatx16& c) {
+  const float4v fa = __builtin_bit_cast(float4v, a), fb = __builtin_bit_cast(float4v, b);
+  c = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[0], fb[0], c, 0, 0, 0);
+  c = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[1], fb[1], c, 0, 0, 0);
+  c = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[2], fb[2], c, 0, 0, 0);
+  c = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[3], fb[3], c, 0, 0, 0);
+}
+
+template <typename T, int BM, int BN, int WGM, int WGN, int BKB>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k_igemm(IgemmParams p) {
   static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
-  static_assert(BK == 32 || BK == 64, "slab depth");
-  constexpr int CPR = BK / 8;                   // 16-byte chunks per slab row
+  static_assert(BKB == 64 || BKB == 128, "slab row bytes");
+  constexpr int ES = (int)sizeof(T);
+  constexpr int BK = BKB / ES;                  // K elements per slab
+  constexpr int CPR = BKB / 16;                 // 16-byte chunks per slab row
   constexpr int RSTEP = 256 / CPR;              // rows covered by one pass of the 256 loader threads
   constexpr int WM = BM / WGM, WN = BN / WGN;   // wave tile
   constexpr int MI = WM / 32, NJ = WN / 32;     // 32x32 MFMA tiles per wave
   constexpr int A_CHUNKS = BM / RSTEP, B_CHUNKS = BN / RSTEP;
-  constexpr int SW = WN + 8;                    // staging row stride of the epilogue (elements)
-  constexpr int SLAB_ELEMS = 2 * (BM + BN) * BK;
-  constexpr int STAGE_ELEMS = 4 * 32 * SW;
-  __shared__ __attribute__((aligned(16))) bf16_t smem[SLAB_ELEMS > STAGE_ELEMS ? SLAB_ELEMS : STAGE_ELEMS];
-  bf16_t* const sA = smem;                      // [2][BM*BK]
-  bf16_t* const sB = smem + 2 * BM * BK;        // [2][BN*BK]
+  constexpr int SW = WN + 16 / ES;              // staging row stride of the epilogue (elements): +16 bytes
+  constexpr int SLAB_BYTES = 2 * (BM + BN) * BKB;
+  constexpr int STAGE_BYTES = 4 * 32 * SW * ES;
+  __shared__ __attribute__((aligned(16))) char smem[SLAB_BYTES > STAGE_BYTES ? SLAB_BYTES : STAGE_BYTES];
+  char* const sA = smem;                        // [2][BM*BKB]
+  char* const sB = smem + 2 * BM * BKB;         // [2][BN*BKB]
   __shared__ float sRed[WGM][2][BN];            // [wave row][sum | sumsq][column]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -82,7 +102,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   // --- loader bookkeeping: thread t moves rows (t / CPR) + RSTEP*i, LDS slot t % CPR of each
   const int slot = tid % CPR;
   const int lrow = tid / CPR;
-  const int fsw = BK == 32 ? ((lrow >> 2) & 3) : ((lrow >> 1) & 7);   // RSTEP*i does not touch these bits
+  const int fsw = BKB == 64 ? ((lrow >> 2) & 3) : ((lrow >> 1) & 7);   // RSTEP*i does not touch these bits
   const int gchunk = slot ^ fsw;
   int a_h[A_CHUNKS], a_w[A_CHUNKS];
   unsigned a_img[A_CHUNKS];                     // byte offset of the sample's image, kOob if the row is past M
@@ -95,13 +115,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
     a_w[i] = (int)(mu % (unsigned)p.Wc);
     const unsigned t = mu / (unsigned)p.Wc;
     a_h[i] = (int)(t % (unsigned)p.Hc);
-    a_img[i] = ok ? (t / (unsigned)p.Hc) * (unsigned)(Hin * Win) * (unsigned)p.Cin * 2u : kOob;
+    a_img[i] = ok ? (t / (unsigned)p.Hc) * (unsigned)(Hin * Win) * (unsigned)p.Cin * (unsigned)ES : kOob;
   }
   unsigned b_off[B_CHUNKS];
 #pragma unroll
   for (int i = 0; i < B_CHUNKS; ++i) {
     const int row = n0 + lrow + i * RSTEP;
-    b_off[i] = row < p.N ? (unsigned)row * (unsigned)p.K * 2u + (unsigned)gchunk * 16u : kOob;
+    b_off[i] = row < p.N ? (unsigned)row * (unsigned)p.K * (unsigned)ES + (unsigned)gchunk * 16u : kOob;
   }
 
   int rs = 0, ci0 = 0;                          // filter tap and first channel of the next slab to load
@@ -111,49 +131,47 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
     const int r_ = rs / p.ksz, s_ = rs - r_ * p.ksz;                                                         \
     _Pragma("unroll") for (int i = 0; i < A_CHUNKS; ++i) {                                                   \
       const int hh = a_h[i] + r_ - pad, ww = a_w[i] + s_ - pad;                                              \
-      const bool ok = hh >= 0 && hh < p.Hc && ww >= 0 && ww < p.Wc;                                          \
+      const bool ok = a_img[i] != kOob && hh >= 0 && hh < p.Hc && ww >= 0 && ww < p.Wc;                      \
       const unsigned pix = (unsigned)((hh >> p.up) * Win + (ww >> p.up));                                    \
-      a_off[i] = ok ? (a_img[i] | 0u) + pix * (unsigned)p.Cin * 2u + (unsigned)gchunk * 16u : kOob;          \
-      if (a_img[i] == kOob) a_off[i] = kOob;                                                                 \
+      a_off[i] = ok ? a_img[i] + pix * (unsigned)p.Cin * (unsigned)ES + (unsigned)gchunk * 16u : kOob;       \
     }                                                                                                        \
   }
 #define IGEMM_LOAD(RA, RB)                                                                                   \
   {                                                                                                          \
     if (ci0 == 0) IGEMM_TAP();                                                                               \
     _Pragma("unroll") for (int i = 0; i < A_CHUNKS; ++i)                                                     \
-        RA[i] = __builtin_amdgcn_raw_buffer_load_b128(rX, a_off[i] + (unsigned)ci0 * 2u, 0, 0);              \
+        RA[i] = __builtin_amdgcn_raw_buffer_load_b128(rX, a_off[i] + (unsigned)ci0 * (unsigned)ES, 0, 0);    \
     _Pragma("unroll") for (int i = 0; i < B_CHUNKS; ++i)                                                     \
         RB[i] = __builtin_amdgcn_raw_buffer_load_b128(rW, b_off[i] + kbyte, 0, 0);                           \
     ci0 += BK;                                                                                               \
-    kbyte += BK * 2;                                                                                         \
+    kbyte += BKB;                                                                                            \
     if (ci0 == p.Cin) { ci0 = 0; ++rs; }                                                                     \
   }
-  const int st_off = lrow * BK + slot * 8;      // this thread's element offset inside a slab buffer (+ i*RSTEP*BK)
+  const int st_off = lrow * BKB + slot * 16;    // this thread's byte offset inside a slab buffer (+ i*RSTEP*BKB)
 #define IGEMM_STORE(BUF, RA, RB)                                                                             \
   {                                                                                                          \
     _Pragma("unroll") for (int i = 0; i < A_CHUNKS; ++i)                                                     \
-        *reinterpret_cast<uint4v*>(&sA[(BUF) * BM * BK + st_off + i * RSTEP * BK]) = RA[i];                  \
+        *reinterpret_cast<uint4v*>(sA + (BUF) * BM * BKB + st_off + i * RSTEP * BKB) = RA[i];                \
     _Pragma("unroll") for (int i = 0; i < B_CHUNKS; ++i)                                                     \
-        *reinterpret_cast<uint4v*>(&sB[(BUF) * BN * BK + st_off + i * RSTEP * BK]) = RB[i];                  \
+        *reinterpret_cast<uint4v*>(sB + (BUF) * BN * BKB + st_off + i * RSTEP * BKB) = RB[i];                \
   }
-  // fragment reads: lane l wants row (l%32) of a 32-row MFMA tile, k-chunk 2*ks + l/32;
+  // fragment reads: lane l wants row (l%32) of a 32-row MFMA tile, chunk 2*ks + l/32;
   // the lane-dependent part of the address is the same for A and B and for every tile
   const int frag_row = lane & 31, frag_c = lane >> 5;
-  const int ffr = BK == 32 ? ((frag_row >> 2) & 3) : ((frag_row >> 1) & 7);
-  int lane_off[BK / 16];
+  const int ffr = BKB == 64 ? ((frag_row >> 2) & 3) : ((frag_row >> 1) & 7);
+  int lane_off[BKB / 32];
 #pragma unroll
-  for (int ks = 0; ks < BK / 16; ++ks) lane_off[ks] = frag_row * BK + (((ks * 2 + frag_c) ^ ffr) * 8);
+  for (int ks = 0; ks < BKB / 32; ++ks) lane_off[ks] = frag_row * BKB + (((ks * 2 + frag_c) ^ ffr) * 16);
 #define IGEMM_COMPUTE(BUF)                                                                                   \
   {                                                                                                          \
-    _Pragma("unroll") for (int ks = 0; ks < BK / 16; ++ks) {                                                 \
-      bf16x8 a[MI], b[NJ];                                                                                   \
+    _Pragma("unroll") for (int ks = 0; ks < BKB / 32; ++ks) {                                                \
+      uint4v a[MI], b[NJ];                                                                                   \
       _Pragma("unroll") for (int i = 0; i < MI; ++i)                                                         \
-          a[i] = *reinterpret_cast<const bf16x8*>(&sA[(BUF) * BM * BK + (wm * WM + i * 32) * BK + lane_off[ks]]); \
+          a[i] = *reinterpret_cast<const uint4v*>(sA + (BUF) * BM * BKB + (wm * WM + i * 32) * BKB + lane_off[ks]); \
       _Pragma("unroll") for (int j = 0; j < NJ; ++j)                                                         \
-          b[j] = *reinterpret_cast<const bf16x8*>(&sB[(BUF) * BN * BK + (wn * WN + j * 32) * BK + lane_off[ks]]); \
+          b[j] = *reinterpret_cast<const uint4v*>(sB + (BUF) * BN * BKB + (wn * WN + j * 32) * BKB + lane_off[ks]); \
       _Pragma("unroll") for (int i = 0; i < MI; ++i)                                                         \
-        _Pragma("unroll") for (int j = 0; j < NJ; ++j)                                                       \
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);             \
+        _Pragma("unroll") for (int j = 0; j < NJ; ++j) mma_step<T>(a[i], b[j], acc[i][j]);                   \
     }                                                                                                        \
   }
 
@@ -193,11 +211,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   //     row = wm*WM + i*32 + (e/4)*8 + (l/32)*4 + e%4,  column = wn*WN + j*32 + l%32
   // Results go through a wave-private LDS staging area (the slab buffers are free now:
   // the K loop ended on a barrier) so that global stores are 16 bytes wide and each
-  // instruction covers whole 2*WN-byte row segments.
-  bf16_t* __restrict__ Y = (bf16_t*)p.y;
+  // instruction covers whole row segments.
+  T* __restrict__ Y = (T*)p.y;
   const int col_lane = lane & 31, row_lane = (lane >> 5) * 4;
-  const bool wide_store = (p.N % 8 == 0) && !p.y_aux;
-  bf16_t* stage = smem + wave * (32 * SW);
+  const bool wide_store = ((p.N * ES) % 16 == 0) && !p.y_aux;
+  T* stage = reinterpret_cast<T*>(smem) + wave * (32 * SW);
   float s1[NJ], s2[NJ];
 #pragma unroll
   for (int j = 0; j < NJ; ++j) { s1[j] = 0.0f; s2[j] = 0.0f; }
@@ -212,27 +230,28 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
       for (int e = 0; e < 16; ++e) {
         const int lr = (e >> 2) * 8 + row_lane + (e & 3);
         const int64_t m = m0 + wm * WM + i * 32 + lr;
-        const float v = bf16_to_f32(f32_to_bf16(acc[i][j][e] + bias));   // the stored conv result
-        if (m < p.M && col_ok) { s1[j] += v; s2[j] = fmaf(v, v, s2[j]); }
+        const float v = round_to_storage<T>(acc[i][j][e] + bias);   // the stored conv result
+        if (p.partial && m < p.M && col_ok) { s1[j] += v; s2[j] = fmaf(v, v, s2[j]); }
         const float a = apply_act(v, p.act);
         if (wide_store) {
-          stage[lr * SW + j * 32 + col_lane] = f32_to_bf16(a);
+          Store<T>::st(&stage[lr * SW + j * 32 + col_lane], a);
         } else if (m < p.M && col_ok) {
-          Y[m * p.N + col] = f32_to_bf16(a);
+          Store<T>::st(&Y[m * p.N + col], a);
           if (p.y_aux) p.y_aux[m * p.N + col] = a;
         }
       }
     }
     if (wide_store) {
-      constexpr int CPR = WN / 8;                // 16-byte chunks per row
+      constexpr int EPC = 16 / ES;               // elements per 16-byte chunk
+      constexpr int CPRO = WN / EPC;             // chunks per staged row
 #pragma unroll
-      for (int c = 0; c < (32 * CPR) / 64; ++c) {
+      for (int c = 0; c < (32 * CPRO) / 64; ++c) {
         const int idx = c * 64 + lane;
-        const int lr = idx / CPR, ch = idx % CPR;
+        const int lr = idx / CPRO, ch = idx % CPRO;
         const int64_t m = m0 + wm * WM + i * 32 + lr;
-        const int col0 = n0 + wn * WN + ch * 8;
+        const int col0 = n0 + wn * WN + ch * EPC;
         if (m < p.M && col0 < p.N)
-          *reinterpret_cast<uint4*>(Y + m * p.N + col0) = *reinterpret_cast<const uint4*>(&stage[lr * SW + ch * 8]);
+          *reinterpret_cast<uint4v*>(Y + m * p.N + col0) = *reinterpret_cast<const uint4v*>(&stage[lr * SW + ch * EPC]);
       }
     }
   }
@@ -259,58 +278,65 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   }
 }
 
-struct IgemmTile { int bm, bn, bk; };
+struct IgemmTile { int bm, bn, bkb; };
 
 // Largest tile that still gives every compute unit about two workgroups.
-IgemmTile pick_tile(int64_t M, int cout, int cin) {
+IgemmTile pick_tile(int64_t M, int cout, int cin, int es) {
   const int bn = cout > 64 ? 128 : 64;
   const int64_t tiles_n = (cout + bn - 1) / bn;
-  int bm = bn == 64 ? 256 : 128;
+  int bm = (bn == 64 && es == 2) ? 256 : 128;
   if (((M + 255) / 256) * tiles_n < 512) bm = 128;
-  int bk = cin % 64 == 0 ? 64 : 32;
-  if (bm == 256) bk = 32;                       // 256x64 with 64-deep slabs exceeds the register / LDS budget of two waves per SIMD
-  return IgemmTile{bm, bn, bk};
+  int bkb = (cin * es) % 128 == 0 ? 128 : 64;
+  if (bm == 256) bkb = 64;                      // 256x64 with 128-byte slabs exceeds the register / LDS budget of two waves per SIMD
+  return IgemmTile{bm, bn, bkb};
 }
 
 }  // namespace
 
 bool conv_mfma_supported(const ConvArgs& a) {
-  if (a.dtype != AE_BF16) return false;
-  if (a.cin % 32 != 0 || a.cout < 32) return false;
+  const int es = (int)dtype_size(a.dtype);
+  if ((a.cin * es) % 64 != 0 || a.cout < 32) return false;
   const int64_t M = (int64_t)a.n * a.hc * a.wc;
-  const int64_t x_bytes = (int64_t)a.n * (a.hc >> a.up) * (a.wc >> a.up) * a.cin * 2;
-  const int64_t w_bytes = (int64_t)a.cout * a.k * a.k * a.cin * 2;
+  const int64_t x_bytes = (int64_t)a.n * (a.hc >> a.up) * (a.wc >> a.up) * a.cin * es;
+  const int64_t w_bytes = (int64_t)a.cout * a.k * a.k * a.cin * es;
   if (x_bytes >= 0x7FFFFFFF || w_bytes >= 0x7FFFFFFF) return false;   // 32-bit buffer offsets
   return M * ((a.cout + 63) / 64) / 128 < 0x7FFFFFFF && M < 0x7FFFFFFF;
 }
 
 int conv_partial_rows(const ConvArgs& a, bool mfma) {
   if (!mfma) return kReduceRows;
-  return pick_tile((int64_t)a.n * a.hc * a.wc, a.cout, a.cin).bm;
+  return pick_tile((int64_t)a.n * a.hc * a.wc, a.cout, a.cin, (int)dtype_size(a.dtype)).bm;
 }
 
 int launch_conv_mfma(const ConvArgs& a, hipStream_t s) {
   if (!conv_mfma_supported(a)) return fail(AE_EINVAL, "conv_mfma: shape not supported");
+  const int es = (int)dtype_size(a.dtype);
   IgemmParams p;
   p.x = a.x; p.w = a.w; p.bias = a.bias; p.y = a.y; p.y_aux = a.y_aux; p.partial = a.partial;
   p.M = (int64_t)a.n * a.hc * a.wc;
   p.N = a.cout; p.K = a.k * a.k * a.cin;
   p.Hc = a.hc; p.Wc = a.wc; p.Cin = a.cin; p.ksz = a.k; p.up = a.up; p.act = a.act;
-  p.x_bytes = (unsigned)((int64_t)a.n * (a.hc >> a.up) * (a.wc >> a.up) * a.cin * 2);
-  p.w_bytes = (unsigned)((int64_t)a.cout * a.k * a.k * a.cin * 2);
-  const IgemmTile t = pick_tile(p.M, a.cout, a.cin);
+  p.x_bytes = (unsigned)((int64_t)a.n * (a.hc >> a.up) * (a.wc >> a.up) * a.cin * es);
+  p.w_bytes = (unsigned)((int64_t)a.cout * a.k * a.k * a.cin * es);
+  const IgemmTile t = pick_tile(p.M, a.cout, a.cin, es);
   p.tiles_n = (a.cout + t.bn - 1) / t.bn;
   const int64_t tiles_m = (p.M + t.bm - 1) / t.bm;
   dim3 grid((unsigned)(tiles_m * p.tiles_n));
-#define IGEMM_LAUNCH(BMV, BNV, GM, GN)                                                              \
-  do {                                                                                              \
-    if (t.bk == 64) hipLaunchKernelGGL((k_igemm_bf16<BMV, BNV, GM, GN, 64>), grid, dim3(256), 0, s, p); \
-    else hipLaunchKernelGGL((k_igemm_bf16<BMV, BNV, GM, GN, 32>), grid, dim3(256), 0, s, p);        \
+#define IGEMM_LAUNCH_T(T, BMV, BNV, GM, GN)                                                            \
+  do {                                                                                                 \
+    if (t.bkb == 128) hipLaunchKernelGGL((k_igemm<T, BMV, BNV, GM, GN, 128>), grid, dim3(256), 0, s, p); \
+    else hipLaunchKernelGGL((k_igemm<T, BMV, BNV, GM, GN, 64>), grid, dim3(256), 0, s, p);             \
   } while (0)
-  if (t.bm == 256) IGEMM_LAUNCH(256, 64, 4, 1);
+#define IGEMM_LAUNCH(BMV, BNV, GM, GN)                                         \
+  do {                                                                         \
+    if (a.dtype == AE_BF16) IGEMM_LAUNCH_T(bf16_t, BMV, BNV, GM, GN);          \
+    else IGEMM_LAUNCH_T(float, BMV, BNV, GM, GN);                              \
+  } while (0)
+  if (t.bm == 256) hipLaunchKernelGGL((k_igemm<bf16_t, 256, 64, 4, 1, 64>), grid, dim3(256), 0, s, p);
   else if (t.bn == 128) IGEMM_LAUNCH(128, 128, 2, 2);
   else IGEMM_LAUNCH(128, 64, 2, 2);
 #undef IGEMM_LAUNCH
+#undef IGEMM_LAUNCH_T
   return launch_status("conv_mfma");
 }
 
@@ -358,16 +384,69 @@ __device__ __forceinline__ bf16x8 lds_tr_frag(const bf16_t* base0, const bf16_t*
   return u.v;
 }
 
-template <int BM, int BN>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k_wgrad_bf16(WgradParams p) {
-  constexpr int BK = 32;                         // pixels per slab
-  constexpr int LA = BM + 16, LB = BN + 16;      // LDS row strides in elements (+32 bytes: 4 rows hit disjoint banks)
+// One slab of MFMAs of the weight-gradient kernel.  sa / sb point at the wave's first
+// channel of the [pixel][channel] slabs.
+template <typename T, int MI, int NJ, int BK, int LA, int LB>
+__device__ __forceinline__ void wgrad_compute(const T* sa, const T* sb, int lane, floatx16 (&acc)[MI][NJ]) {
+  if constexpr (sizeof(T) == 2) {
+    // transposing-load geometry of this lane: 16-lane group G covers channels 16*(G&1).. of
+    // the 32-channel MFMA tile and pixels 8*(G>>1)..; local lane sl addresses pixel sl/4,
+    // channels 4*(sl%4)..
+    const int grp = lane >> 4, sl = lane & 15;
+    const int t_pix = 8 * (grp >> 1) + (sl >> 2);
+    const int t_ch = 16 * (grp & 1) + 4 * (sl & 3);
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      bf16x8 a[MI], bb[NJ];
+#pragma unroll
+      for (int i = 0; i < MI; ++i) {
+        const bf16_t* q = &sa[(ks * 16 + t_pix) * LA + i * 32 + t_ch];
+        a[i] = lds_tr_frag(q, q + 4 * LA);
+      }
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) {
+        const bf16_t* q = &sb[(ks * 16 + t_pix) * LB + j * 32 + t_ch];
+        bb[j] = lds_tr_frag(q, q + 4 * LB);
+      }
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bb[j], acc[i][j], 0, 0, 0);
+    }
+  } else {
+    // fp32: lane l supplies channel l%32 of pixel 2*st + l/32 — a plain 4-byte read
+    const int ch = lane & 31, half = lane >> 5;
+#pragma unroll
+    for (int st = 0; st < BK / 2; ++st) {
+      float a[MI], bb[NJ];
+#pragma unroll
+      for (int i = 0; i < MI; ++i) a[i] = sa[(2 * st + half) * LA + i * 32 + ch];
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) bb[j] = sb[(2 * st + half) * LB + j * 32 + ch];
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], bb[j], acc[i][j], 0, 0, 0);
+    }
+  }
+}
+
+template <typename T, int BM, int BN>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k_wgrad(WgradParams p) {
+  constexpr int ES = (int)sizeof(T);
+  constexpr int EPC = 16 / ES;                   // elements per 16-byte chunk
+  constexpr int BK = ES == 2 ? 32 : 16;          // pixels per slab
+  // LDS row strides in elements.  bf16: +32 bytes, so that the 4 pixel rows a transposing
+  // load touches hit disjoint banks; fp32: +128 bytes, so that the two pixel rows a 64-lane
+  // 4-byte read touches are 32 banks apart.
+  constexpr int LPAD = ES == 2 ? 16 : 32;
+  constexpr int LA = BM + LPAD, LB = BN + LPAD;
   constexpr int WM = BM / 2, WN = BN / 2;
   constexpr int MI = WM / 32, NJ = WN / 32;
-  constexpr int A_TPR = BM / 8, B_TPR = BN / 8;  // 16-byte chunks per pixel row
+  constexpr int A_TPR = BM / EPC, B_TPR = BN / EPC;  // 16-byte chunks per pixel row
   constexpr int A_CHUNKS = BK * A_TPR / 256, B_CHUNKS = BK * B_TPR / 256;
-  __shared__ __attribute__((aligned(16))) bf16_t sA[2][BK * LA];
-  __shared__ __attribute__((aligned(16))) bf16_t sB[2][BK * LB];
+  __shared__ __attribute__((aligned(16))) T sA[2][BK * LA];
+  __shared__ __attribute__((aligned(16))) T sB[2][BK * LB];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
@@ -383,8 +462,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   const int pad = (p.ksz - 1) >> 1;
   const int co0 = tm * BM, ci0 = tn * BN;
   const int Hin = p.Hc >> p.up, Win = p.Wc >> p.up;
-  const bf16_t* __restrict__ X = (const bf16_t*)p.x;
-  const bf16_t* __restrict__ DY = (const bf16_t*)p.dy;
+  const T* __restrict__ X = (const T*)p.x;
+  const T* __restrict__ DY = (const T*)p.dy;
   const int64_t m_begin = (int64_t)split * p.rows_per_split;
   const int64_t m_end = (m_begin + p.rows_per_split < p.M) ? m_begin + p.rows_per_split : p.M;
   const int KT = (int)((m_end - m_begin + BK - 1) / BK);
@@ -399,7 +478,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
       const int id = tid + i * 256;                                                                          \
       const int64_t m = mb + id / A_TPR;                                                                     \
       const bool ok = m < m_end;                                                                             \
-      uint4 v = *reinterpret_cast<const uint4*>(DY + (ok ? m : m_end - 1) * p.Cout + co0 + (id % A_TPR) * 8); \
+      uint4 v = *reinterpret_cast<const uint4*>(DY + (ok ? m : m_end - 1) * p.Cout + co0 + (id % A_TPR) * EPC); \
       if (!ok) { v.x = 0u; v.y = 0u; v.z = 0u; v.w = 0u; }                                                   \
       RA[i] = v;                                                                                             \
     }                                                                                                        \
@@ -413,7 +492,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
       const bool ok = m < m_end && hh >= 0 && hh < p.Hc && ww >= 0 && ww < p.Wc;                             \
       const int hc_ = min(max(hh, 0), p.Hc - 1), wc_ = min(max(ww, 0), p.Wc - 1);                            \
       uint4 v = *reinterpret_cast<const uint4*>(X + (((int64_t)n * Hin + (hc_ >> p.up)) * Win + (wc_ >> p.up)) * p.Cin + \
-                                                ci0 + (id % B_TPR) * 8);                                     \
+                                                ci0 + (id % B_TPR) * EPC);                                   \
       if (!ok) { v.x = 0u; v.y = 0u; v.z = 0u; v.w = 0u; }                                                   \
       RB[i] = v;                                                                                             \
     }                                                                                                        \
@@ -423,30 +502,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   {                                                                                                          \
     _Pragma("unroll") for (int i = 0; i < A_CHUNKS; ++i) {                                                   \
       const int id = tid + i * 256;                                                                          \
-      *reinterpret_cast<uint4*>(&sA[BUF][(id / A_TPR) * LA + (id % A_TPR) * 8]) = RA[i];                     \
+      *reinterpret_cast<uint4*>(&sA[BUF][(id / A_TPR) * LA + (id % A_TPR) * EPC]) = RA[i];                   \
     }                                                                                                        \
     _Pragma("unroll") for (int i = 0; i < B_CHUNKS; ++i) {                                                   \
       const int id = tid + i * 256;                                                                          \
-      *reinterpret_cast<uint4*>(&sB[BUF][(id / B_TPR) * LB + (id % B_TPR) * 8]) = RB[i];                     \
+      *reinterpret_cast<uint4*>(&sB[BUF][(id / B_TPR) * LB + (id % B_TPR) * EPC]) = RB[i];                   \
     }                                                                                                        \
   }
-#define WGRAD_COMPUTE(BUF)                                                                                   \
-  {                                                                                                          \
-    _Pragma("unroll") for (int ks = 0; ks < BK / 16; ++ks) {                                                 \
-      bf16x8 a[MI], bb[NJ];                                                                                  \
-      _Pragma("unroll") for (int i = 0; i < MI; ++i) {                                                       \
-        const bf16_t* q = &sA[BUF][(ks * 16 + t_pix) * LA + wm * WM + i * 32 + t_ch];                        \
-        a[i] = lds_tr_frag(q, q + 4 * LA);                                                                   \
-      }                                                                                                      \
-      _Pragma("unroll") for (int j = 0; j < NJ; ++j) {                                                       \
-        const bf16_t* q = &sB[BUF][(ks * 16 + t_pix) * LB + wn * WN + j * 32 + t_ch];                        \
-        bb[j] = lds_tr_frag(q, q + 4 * LB);                                                                  \
-      }                                                                                                      \
-      _Pragma("unroll") for (int i = 0; i < MI; ++i)                                                         \
-        _Pragma("unroll") for (int j = 0; j < NJ; ++j)                                                       \
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bb[j], acc[i][j], 0, 0, 0);            \
-    }                                                                                                        \
-  }
+#define WGRAD_COMPUTE(BUF) wgrad_compute<T, MI, NJ, BK, LA, LB>(&sA[BUF][wm * WM], &sB[BUF][wn * WN], lane, acc)
 
   floatx16 acc[MI][NJ];
 #pragma unroll
@@ -455,13 +518,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
     for (int j = 0; j < NJ; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
-
-  // transposing-load geometry of this lane: 16-lane group G covers channels 16*(G&1).. of
-  // the 32-channel MFMA tile and pixels 8*(G>>1)..; local lane sl addresses pixel sl/4,
-  // channels 4*(sl%4)..
-  const int grp = lane >> 4, sl = lane & 15;
-  const int t_pix = 8 * (grp >> 1) + (sl >> 2);
-  const int t_ch = 16 * (grp & 1) + 4 * (sl & 3);
 
   // KT >= 1: every split owns at least one pixel (the host sizes the splits that way)
   uint4 ra0[A_CHUNKS], rb0[B_CHUNKS], ra1[A_CHUNKS], rb1[B_CHUNKS];
@@ -539,9 +595,7 @@ WgradPlan plan_wgrad(int cout, int cin, int k, int64_t rows) {
 }  // namespace
 
 bool wgrad_mfma_supported(const WgradArgs& a) {
-  if (a.dtype != AE_BF16) return false;
   if (a.cin % 64 != 0 || a.cout % 64 != 0) return false;
-  if (a.cin % 128 != 0 && a.cout % 128 != 0 && false) return false;
   const int64_t rows = (int64_t)a.n * a.hc * a.wc;
   return rows < 0x7FFFFFFF;
 }
@@ -563,10 +617,16 @@ int launch_wgrad_mfma(const WgradArgs& a, float* workspace, hipStream_t s) {
   const int64_t blocks = (int64_t)w.splits * w.tiles_m * w.tiles_n * a.k * a.k;
   if (blocks > 0x7FFFFFFF) return fail(AE_EINVAL, "wgrad_mfma: grid too large");
   dim3 grid((unsigned)blocks);
-  if (w.bm == 128 && w.bn == 128) hipLaunchKernelGGL((k_wgrad_bf16<128, 128>), grid, dim3(256), 0, s, p);
-  else if (w.bm == 128) hipLaunchKernelGGL((k_wgrad_bf16<128, 64>), grid, dim3(256), 0, s, p);
-  else if (w.bn == 128) hipLaunchKernelGGL((k_wgrad_bf16<64, 128>), grid, dim3(256), 0, s, p);
-  else hipLaunchKernelGGL((k_wgrad_bf16<64, 64>), grid, dim3(256), 0, s, p);
+#define WGRAD_LAUNCH(T)                                                                              \
+  do {                                                                                               \
+    if (w.bm == 128 && w.bn == 128) hipLaunchKernelGGL((k_wgrad<T, 128, 128>), grid, dim3(256), 0, s, p); \
+    else if (w.bm == 128) hipLaunchKernelGGL((k_wgrad<T, 128, 64>), grid, dim3(256), 0, s, p);       \
+    else if (w.bn == 128) hipLaunchKernelGGL((k_wgrad<T, 64, 128>), grid, dim3(256), 0, s, p);       \
+    else hipLaunchKernelGGL((k_wgrad<T, 64, 64>), grid, dim3(256), 0, s, p);                         \
+  } while (0)
+  if (a.dtype == AE_BF16) WGRAD_LAUNCH(bf16_t);
+  else WGRAD_LAUNCH(float);
+#undef WGRAD_LAUNCH
   AE_TRY(launch_status("wgrad_mfma"));
   const int64_t total = (int64_t)a.cout * a.cin * a.k * a.k;
   int64_t g = (total + 255) / 256;

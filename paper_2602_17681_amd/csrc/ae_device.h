@@ -11,12 +11,11 @@ typedef uint16_t bf16_t;  // raw bfloat16 bit pattern
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t b) { return __uint_as_float((uint32_t)b << 16); }
 
-// round to nearest, ties to even (NaN kept quiet)
+// round to nearest, ties to even: gfx950 has a hardware conversion (v_cvt_pk_bf16_f32),
+// which the compiler selects for a float -> __bf16 cast
 __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (bf16_t)((u >> 16) | 0x40u);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
+  const __bf16 h = (__bf16)f;
+  return __builtin_bit_cast(bf16_t, h);
 }
 
 template <typename T> struct Store;
