@@ -90,20 +90,34 @@ def kernel_table(st, steps):
     return rows
 
 
+FAMILY = {"conv_mfma": "k_igemm", "dgrad_mfma": "k_igemm", "wgrad_mfma": "k_wgrad",
+          "conv_thin_in_mfma": "k_thin_in_mfma", "dgrad_thin_mfma": "k_thin_in_mfma"}
+
+
 def roofline_of(rows, dtype):
-    """The kernel launch that takes the most time per step, priced against the roof that bounds it."""
+    """The kernel that takes the largest share of the step (all its launches together), priced
+    against the roof that bounds it: total algorithmic FLOPs (or bytes) of its launches divided by
+    their total HIP-event time, i.e. per-launch average work over per-launch average duration."""
     if not rows:
         return None
-    top = max(rows, key=lambda r: r["ms_per_step"])
-    if top["flops"] > 0:
-        # machine balance decides: a conv launch whose arithmetic intensity is below peak_flops/peak_bw is HBM-bound
-        ai = top["flops"] / max(top["bytes"], 1.0)
-        balance = PEAK[dtype] * 1e12 / (HBM_PEAK_GBS * 1e9)
-        if ai >= balance:
-            return dict(bound="mfma", kernel=top["name"], achieved=top["tflops"], peak=PEAK[dtype], unit="TFLOP/s",
-                        frac=top["tflops"] / PEAK[dtype], traffic=None, avg_ms=top["avg_ms"])
-    return dict(bound="hbm", kernel=top["name"], achieved=top["gbs"], peak=HBM_PEAK_GBS, unit="GB/s",
-                frac=(top["gbs"] or 0.0) / HBM_PEAK_GBS, traffic=None, avg_ms=top["avg_ms"])
+    fam = {}
+    for r in rows:
+        key = FAMILY.get(r["name"].split(".")[-1], r["name"].split(".")[-1])
+        f = fam.setdefault(key, dict(ms=0.0, flops=0.0, bytes=0.0, launches=0))
+        f["ms"] += r["ms_per_step"]
+        f["flops"] += r["flops"]
+        f["bytes"] += r["bytes"]
+        f["launches"] += 1
+    name, top = max(fam.items(), key=lambda kv: kv[1]["ms"])
+    avg_ms = top["ms"] / top["launches"]
+    balance = PEAK[dtype] * 1e12 / (HBM_PEAK_GBS * 1e9)
+    if top["flops"] > 0 and top["flops"] / max(top["bytes"], 1.0) >= balance:
+        ach = top["flops"] / top["ms"] / 1e9
+        return dict(bound="mfma", kernel=name, achieved=ach, peak=PEAK[dtype], unit="TFLOP/s", frac=ach / PEAK[dtype],
+                    traffic=None, avg_ms=avg_ms, launches_per_step=top["launches"], flops_per_launch=top["flops"] / top["launches"])
+    ach = top["bytes"] / top["ms"] / 1e6
+    return dict(bound="hbm", kernel=name, achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS,
+                traffic=None, avg_ms=avg_ms, launches_per_step=top["launches"], bytes_per_launch=top["bytes"] / top["launches"])
 
 
 def cpu_baseline(name, budget_s=20.0):

@@ -556,7 +556,7 @@ int launch_thin_out_conv(const void* wide, const float* wcanon, const float* bia
 }
 
 int64_t thin_wgrad_workspace_floats(int64_t q_pixels, int ct, int cw) {
-  const int64_t ppb = 2048;
+  const int64_t ppb = 8192;
   return ((q_pixels + ppb - 1) / ppb) * 9 * ct * cw;
 }
 
@@ -567,7 +567,7 @@ int launch_thin_wgrad(const void* thin, const void* wide, float* workspace, floa
   if (ct < 1 || ct > 4) return fail(AE_EINVAL, "thin_wgrad: thin side must have 1..4 channels");
   const int64_t Q = (int64_t)n * hq * wq;
   if (Q >= 0x7FFFFFFF) return fail(AE_EINVAL, "thin_wgrad: tensor too large");
-  const int ppb = 2048;
+  const int ppb = 8192;
   const int nblocks = (int)((Q + ppb - 1) / ppb);
   int slice = 64;                               // wide channels per block
   while (slice > cw && slice > 1) slice >>= 1;
