@@ -237,9 +237,13 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
   TIMED(si, "bwd.bias_finalize", 0.0, 0.0,
         launch_colsum_finalize(m->partial, nblocks_for(rows), st.cout, grads + st.b_off, s));
   if (st.thin == 1) {
-    TIMED(si, "bwd.wgrad_thin", conv_flops, (in_el + raw_el) * es + wel * 4,
-          launch_thin_wgrad(in, dr, m->wgrad_ws, grads + st.w_off, P.batch, st.hc, st.wc, st.cin, st.cout, 0, 0, P.dtype,
-                            s));
+    if (thin_wgrad_mfma_supported(st.cin, st.cout, st.wc, P.dtype))
+      TIMED(si, "bwd.wgrad_thin_mfma", conv_flops, (in_el + raw_el) * es + wel * 4,
+            launch_thin_wgrad_mfma(in, dr, m->wgrad_ws, grads + st.w_off, P.batch, st.hc, st.wc, st.cin, st.cout, s));
+    else
+      TIMED(si, "bwd.wgrad_thin", conv_flops, (in_el + raw_el) * es + wel * 4,
+            launch_thin_wgrad(in, dr, m->wgrad_ws, grads + st.w_off, P.batch, st.hc, st.wc, st.cin, st.cout, 0, 0,
+                              P.dtype, s));
     return AE_OK;   // the first layer needs no input gradient
   }
   // weight gradient

@@ -265,8 +265,12 @@ int build_plan(const char* spec, int batch, int dtype, int bn_mode, Plan* plan) 
       wa.x = wa.dy = nullptr; wa.dw_canonical = nullptr;
       wa.n = batch; wa.hc = st.hc; wa.wc = st.wc; wa.cin = st.cin; wa.cout = st.cout; wa.k = st.k; wa.up = st.up;
       wa.dtype = dtype;
-      if (st.thin == 1)
+      if (st.thin == 1) {
         plan->max_wgrad_floats = std::max(plan->max_wgrad_floats, thin_wgrad_workspace_floats(rows, st.cin, st.cout));
+        if (thin_wgrad_mfma_supported(st.cin, st.cout, st.wc, dtype))
+          plan->max_wgrad_floats = std::max(plan->max_wgrad_floats,
+                                            thin_wgrad_mfma_workspace_floats(batch, st.hc, st.wc, st.cout));
+      }
       else if (st.thin == 2)
         plan->max_wgrad_floats = std::max(plan->max_wgrad_floats,
                                           thin_wgrad_workspace_floats(B * st.hin * st.win, st.cout, st.cin));
