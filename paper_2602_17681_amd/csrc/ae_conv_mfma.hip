@@ -372,6 +372,8 @@ struct WgradParams {
   int tiles_m, tiles_n; // tiles over C_out and over C_in
   int rows_per_split;   // multiple of 32
   int K;                // k*k*C_in
+  int log_w, log_h;     // log2 of Wc / Hc when both are powers of two (POW2 kernels)
+  unsigned x_bytes, dy_bytes;
 };
 
 __device__ __forceinline__ bf16x8 lds_tr_frag(const bf16_t* base0, const bf16_t* base1) {
@@ -431,15 +433,15 @@ __device__ __forceinline__ void wgrad_compute(const T* sa, const T* sb, int lane
   }
 }
 
-template <typename T, int BM, int BN>
+template <typename T, int BM, int BN, bool POW2>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k_wgrad(WgradParams p) {
   constexpr int ES = (int)sizeof(T);
   constexpr int EPC = 16 / ES;                   // elements per 16-byte chunk
   constexpr int BK = ES == 2 ? 32 : 16;          // pixels per slab
-  // LDS row strides in elements.  bf16: +32 bytes, so that the 4 pixel rows a transposing
-  // load touches hit disjoint banks; fp32: +128 bytes, so that the two pixel rows a 64-lane
-  // 4-byte read touches are 32 banks apart.
-  constexpr int LPAD = ES == 2 ? 16 : 32;
+  // LDS row strides in elements (64 banks).  bf16: +64 bytes: 32 lanes of a transposing
+  // load touch 4 pixel rows x 64 bytes, which then tile the 256-byte bank space; fp32:
+  // +128 bytes, so that the two pixel rows a 64-lane 4-byte read touches are 32 banks apart.
+  constexpr int LPAD = 32;
   constexpr int LA = BM + LPAD, LB = BN + LPAD;
   constexpr int WM = BM / 2, WN = BN / 2;
   constexpr int MI = WM / 32, NJ = WN / 32;
@@ -462,14 +464,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   const int pad = (p.ksz - 1) >> 1;
   const int co0 = tm * BM, ci0 = tn * BN;
   const int Hin = p.Hc >> p.up, Win = p.Wc >> p.up;
-  const T* __restrict__ X = (const T*)p.x;
-  const T* __restrict__ DY = (const T*)p.dy;
   const int64_t m_begin = (int64_t)split * p.rows_per_split;
   const int64_t m_end = (m_begin + p.rows_per_split < p.M) ? m_begin + p.rows_per_split : p.M;
   const int KT = (int)((m_end - m_begin + BK - 1) / BK);
 
-  // Loads always go to valid addresses (clamped pixel and coordinates); rows past the
-  // split's end and taps that fall into the zero padding are zeroed in registers.
+  // Buffer loads: rows past the split's end and taps that fall into the zero padding get an
+  // offset beyond the tensor and read as zero.  Pixel coordinates come from shifts when the
+  // image sides are powers of two (POW2), from divisions otherwise.
+  const __amdgpu_buffer_rsrc_t rX = make_rsrc(p.x, p.x_bytes);
+  const __amdgpu_buffer_rsrc_t rDY = make_rsrc(p.dy, p.dy_bytes);
+  const unsigned a_col = (unsigned)(co0 * ES);   // + chunk below
+  const unsigned b_col = (unsigned)(ci0 * ES);
   int kload = 0;
 #define WGRAD_LOAD(RA, RB)                                                                                   \
   {                                                                                                          \
@@ -477,24 +482,25 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
     _Pragma("unroll") for (int i = 0; i < A_CHUNKS; ++i) {                                                   \
       const int id = tid + i * 256;                                                                          \
       const int64_t m = mb + id / A_TPR;                                                                     \
-      const bool ok = m < m_end;                                                                             \
-      uint4 v = *reinterpret_cast<const uint4*>(DY + (ok ? m : m_end - 1) * p.Cout + co0 + (id % A_TPR) * EPC); \
-      if (!ok) { v.x = 0u; v.y = 0u; v.z = 0u; v.w = 0u; }                                                   \
-      RA[i] = v;                                                                                             \
+      const unsigned off = m < m_end ? (unsigned)m * (unsigned)(p.Cout * ES) + a_col + (unsigned)(id % A_TPR) * 16u : kOob; \
+      RA[i] = __builtin_amdgcn_raw_buffer_load_b128(rDY, off, 0, 0);                                         \
     }                                                                                                        \
     _Pragma("unroll") for (int i = 0; i < B_CHUNKS; ++i) {                                                   \
       const int id = tid + i * 256;                                                                          \
       const int64_t m = mb + id / B_TPR;                                                                     \
-      const unsigned mm = (unsigned)(m < m_end ? m : m_end - 1);                                             \
-      const unsigned w = mm % (unsigned)p.Wc, t = mm / (unsigned)p.Wc;                                       \
-      const unsigned h = t % (unsigned)p.Hc, n = t / (unsigned)p.Hc;                                         \
+      const unsigned mm = (unsigned)m;                                                                       \
+      unsigned w, h, n;                                                                                      \
+      if (POW2) {                                                                                            \
+        w = mm & (unsigned)(p.Wc - 1); h = (mm >> p.log_w) & (unsigned)(p.Hc - 1); n = mm >> (p.log_w + p.log_h); \
+      } else {                                                                                               \
+        w = mm % (unsigned)p.Wc; const unsigned t = mm / (unsigned)p.Wc;                                     \
+        h = t % (unsigned)p.Hc; n = t / (unsigned)p.Hc;                                                      \
+      }                                                                                                      \
       const int hh = (int)h + r - pad, ww = (int)w + s - pad;                                                \
       const bool ok = m < m_end && hh >= 0 && hh < p.Hc && ww >= 0 && ww < p.Wc;                             \
-      const int hc_ = min(max(hh, 0), p.Hc - 1), wc_ = min(max(ww, 0), p.Wc - 1);                            \
-      uint4 v = *reinterpret_cast<const uint4*>(X + (((int64_t)n * Hin + (hc_ >> p.up)) * Win + (wc_ >> p.up)) * p.Cin + \
-                                                ci0 + (id % B_TPR) * EPC);                                   \
-      if (!ok) { v.x = 0u; v.y = 0u; v.z = 0u; v.w = 0u; }                                                   \
-      RB[i] = v;                                                                                             \
+      const unsigned pix = (n * (unsigned)Hin + (unsigned)(hh >> p.up)) * (unsigned)Win + (unsigned)(ww >> p.up); \
+      const unsigned off = ok ? pix * (unsigned)(p.Cin * ES) + b_col + (unsigned)(id % B_TPR) * 16u : kOob;  \
+      RB[i] = __builtin_amdgcn_raw_buffer_load_b128(rX, off, 0, 0);                                          \
     }                                                                                                        \
     ++kload;                                                                                                 \
   }
@@ -502,11 +508,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   {                                                                                                          \
     _Pragma("unroll") for (int i = 0; i < A_CHUNKS; ++i) {                                                   \
       const int id = tid + i * 256;                                                                          \
-      *reinterpret_cast<uint4*>(&sA[BUF][(id / A_TPR) * LA + (id % A_TPR) * EPC]) = RA[i];                   \
+      *reinterpret_cast<uint4v*>(&sA[BUF][(id / A_TPR) * LA + (id % A_TPR) * EPC]) = RA[i];                  \
     }                                                                                                        \
     _Pragma("unroll") for (int i = 0; i < B_CHUNKS; ++i) {                                                   \
       const int id = tid + i * 256;                                                                          \
-      *reinterpret_cast<uint4*>(&sB[BUF][(id / B_TPR) * LB + (id % B_TPR) * EPC]) = RB[i];                   \
+      *reinterpret_cast<uint4v*>(&sB[BUF][(id / B_TPR) * LB + (id % B_TPR) * EPC]) = RB[i];                  \
     }                                                                                                        \
   }
 #define WGRAD_COMPUTE(BUF) wgrad_compute<T, MI, NJ, BK, LA, LB>(&sA[BUF][wm * WM], &sB[BUF][wn * WN], lane, acc)
@@ -520,7 +526,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
   // KT >= 1: every split owns at least one pixel (the host sizes the splits that way)
-  uint4 ra0[A_CHUNKS], rb0[B_CHUNKS], ra1[A_CHUNKS], rb1[B_CHUNKS];
+  uint4v ra0[A_CHUNKS], rb0[B_CHUNKS], ra1[A_CHUNKS], rb1[B_CHUNKS];
   WGRAD_LOAD(ra0, rb0);
   if (KT > 1) WGRAD_LOAD(ra1, rb1);
   WGRAD_STORE(0, ra0, rb0);
@@ -596,6 +602,9 @@ WgradPlan plan_wgrad(int cout, int cin, int k, int64_t rows) {
 
 bool wgrad_mfma_supported(const WgradArgs& a) {
   if (a.cin % 64 != 0 || a.cout % 64 != 0) return false;
+  const int64_t es = (int64_t)dtype_size(a.dtype);
+  if ((int64_t)a.n * a.hc * a.wc * a.cout * es >= 0x7FFFFFFF) return false;                    // 32-bit buffer offsets
+  if ((int64_t)a.n * (a.hc >> a.up) * (a.wc >> a.up) * a.cin * es >= 0x7FFFFFFF) return false;
   const int64_t rows = (int64_t)a.n * a.hc * a.wc;
   return rows < 0x7FFFFFFF;
 }
@@ -614,18 +623,33 @@ int launch_wgrad_mfma(const WgradArgs& a, float* workspace, hipStream_t s) {
   p.M = rows; p.Cout = a.cout; p.Cin = a.cin; p.Hc = a.hc; p.Wc = a.wc; p.ksz = a.k; p.up = a.up;
   p.tiles_m = w.tiles_m; p.tiles_n = w.tiles_n; p.rows_per_split = w.rows_per_split;
   p.K = a.k * a.k * a.cin;
+  const int64_t es = (int64_t)dtype_size(a.dtype);
+  p.dy_bytes = (unsigned)(rows * a.cout * es);
+  p.x_bytes = (unsigned)((int64_t)a.n * (a.hc >> a.up) * (a.wc >> a.up) * a.cin * es);
+  const bool pow2 = (a.hc & (a.hc - 1)) == 0 && (a.wc & (a.wc - 1)) == 0;
+  p.log_w = p.log_h = 0;
+  if (pow2) {
+    while ((1 << p.log_w) < a.wc) ++p.log_w;
+    while ((1 << p.log_h) < a.hc) ++p.log_h;
+  }
   const int64_t blocks = (int64_t)w.splits * w.tiles_m * w.tiles_n * a.k * a.k;
   if (blocks > 0x7FFFFFFF) return fail(AE_EINVAL, "wgrad_mfma: grid too large");
   dim3 grid((unsigned)blocks);
-#define WGRAD_LAUNCH(T)                                                                              \
-  do {                                                                                               \
-    if (w.bm == 128 && w.bn == 128) hipLaunchKernelGGL((k_wgrad<T, 128, 128>), grid, dim3(256), 0, s, p); \
-    else if (w.bm == 128) hipLaunchKernelGGL((k_wgrad<T, 128, 64>), grid, dim3(256), 0, s, p);       \
-    else if (w.bn == 128) hipLaunchKernelGGL((k_wgrad<T, 64, 128>), grid, dim3(256), 0, s, p);       \
-    else hipLaunchKernelGGL((k_wgrad<T, 64, 64>), grid, dim3(256), 0, s, p);                         \
+#define WGRAD_LAUNCH_P(T, P2)                                                                           \
+  do {                                                                                                  \
+    if (w.bm == 128 && w.bn == 128) hipLaunchKernelGGL((k_wgrad<T, 128, 128, P2>), grid, dim3(256), 0, s, p); \
+    else if (w.bm == 128) hipLaunchKernelGGL((k_wgrad<T, 128, 64, P2>), grid, dim3(256), 0, s, p);      \
+    else if (w.bn == 128) hipLaunchKernelGGL((k_wgrad<T, 64, 128, P2>), grid, dim3(256), 0, s, p);      \
+    else hipLaunchKernelGGL((k_wgrad<T, 64, 64, P2>), grid, dim3(256), 0, s, p);                        \
+  } while (0)
+#define WGRAD_LAUNCH(T)                      \
+  do {                                       \
+    if (pow2) WGRAD_LAUNCH_P(T, true);       \
+    else WGRAD_LAUNCH_P(T, false);           \
   } while (0)
   if (a.dtype == AE_BF16) WGRAD_LAUNCH(bf16_t);
   else WGRAD_LAUNCH(float);
+#undef WGRAD_LAUNCH_P
 #undef WGRAD_LAUNCH
   AE_TRY(launch_status("wgrad_mfma"));
   const int64_t total = (int64_t)a.cout * a.cin * a.k * a.k;

@@ -227,6 +227,7 @@ LAYERS_BF16 = [
     ("in:64x4x4,conv1:128,sigmoid", 8),
     ("in:3x16x16,conv3:64,bn,relu,pool2", 4),
     ("in:64x8x8,up2,conv3:3,sigmoid", 4),
+    ("in:64x6x10,conv3:128,relu,up2,conv3:64", 3),      # sides that are not powers of two, ragged tiles
 ]
 
 
