@@ -189,6 +189,7 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
   const double out_el = (double)P.batch * st.cout * st.hout * st.wout;
   const double conv_flops = 2.0 * raw_el * st.cin * st.k * st.k;
   const void* dr = g;  // gradient w.r.t. the conv output (bias included)
+  bool bias_done = st.has_bn;   // a batch-norm step gets its bias gradient from bn_bwd_finalize
   if (st.has_bn || st.pool) {
     if (st.has_bn) {
       const int64_t prow = (int64_t)P.batch * st.hout * st.wout;
@@ -196,17 +197,25 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
             launch_post_bwd_reduce(st.raw, g, st.bn_vec, P.batch, st.hc, st.wc, st.cout, st.act, st.pool, P.dtype,
                                    m->partial, s));
       TIMED(si, "bwd.bn_finalize", 0.0, 0.0,
-            launch_bn_bwd_finalize(m->partial, nblocks_for(prow), rows, st.cout, params + st.bn_off, st.bn_vec,
+            launch_bn_bwd_finalize(m->partial, nblocks_for(prow), rows, st.cout, grads + st.b_off, st.bn_vec,
                                    grads + st.bn_off, P.bn_mode == 0, s));
     }
     TIMED(si, "bwd.bn_act_pool", 0.0, (2.0 * raw_el + out_el) * es,
           launch_post_bwd_apply(st.raw, g, st.has_bn ? st.bn_vec : nullptr, m->draw, P.batch, st.hc, st.wc, st.cout,
                                 st.act, st.pool, st.has_bn, P.dtype, s));
     dr = m->draw;
-  } else if (st.act != ACT_NONE) {
+  } else if (st.act != ACT_NONE && st.thin == 2) {
     TIMED(si, "bwd.act", 0.0, 3.0 * raw_el * es,
           launch_act_bwd(st.out, st.aux, g, m->draw, rows * st.cout, st.act, P.dtype, s));
     dr = m->draw;
+  } else if (st.act != ACT_NONE) {
+    // activation backward and the bias gradient's column sums in one pass
+    TIMED(si, "bwd.act_colsum", 0.0, 3.0 * raw_el * es,
+          launch_act_bwd_colsum(st.out, st.aux, g, m->draw, rows, st.cout, st.act, P.dtype, m->partial, s));
+    dr = m->draw;
+    bias_done = true;
+    TIMED(si, "bwd.bias_finalize", 0.0, 0.0,
+          launch_colsum_finalize(m->partial, nblocks_for(rows), st.cout, grads + st.b_off, s));
   }
   if (st.thin == 2) {
     // dr is planar [n][C_out][H][W]
@@ -233,9 +242,11 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
     return AE_OK;
   }
   // bias gradient: column sums of the conv-output gradient
-  TIMED(si, "bwd.bias_colsum", 0.0, raw_el * es, launch_col_stats(dr, rows, st.cout, P.dtype, m->partial, s));
-  TIMED(si, "bwd.bias_finalize", 0.0, 0.0,
-        launch_colsum_finalize(m->partial, nblocks_for(rows), st.cout, grads + st.b_off, s));
+  if (!bias_done) {
+    TIMED(si, "bwd.bias_colsum", 0.0, raw_el * es, launch_col_stats(dr, rows, st.cout, P.dtype, m->partial, s));
+    TIMED(si, "bwd.bias_finalize", 0.0, 0.0,
+          launch_colsum_finalize(m->partial, nblocks_for(rows), st.cout, grads + st.b_off, s));
+  }
   if (st.thin == 1) {
     if (thin_wgrad_mfma_supported(st.cin, st.cout, st.wc, P.dtype))
       TIMED(si, "bwd.wgrad_thin_mfma", conv_flops, (in_el + raw_el) * es + wel * 4,

@@ -284,10 +284,10 @@ struct IgemmTile { int bm, bn, bkb; };
 IgemmTile pick_tile(int64_t M, int cout, int cin, int es) {
   const int bn = cout > 64 ? 128 : 64;
   const int64_t tiles_n = (cout + bn - 1) / bn;
-  int bm = (bn == 64 && es == 2) ? 256 : 128;
+  int bm = es == 2 ? 256 : 128;                 // 256-row tiles: bf16 only (register budget)
   if (((M + 255) / 256) * tiles_n < 512) bm = 128;
   int bkb = (cin * es) % 128 == 0 ? 128 : 64;
-  if (bm == 256) bkb = 64;                      // 256x64 with 128-byte slabs exceeds the register / LDS budget of two waves per SIMD
+  if (bm == 256) bkb = 64;                      // 256-row tiles with 128-byte slabs exceed the budget of two waves per SIMD
   return IgemmTile{bm, bn, bkb};
 }
 
@@ -332,7 +332,8 @@ int launch_conv_mfma(const ConvArgs& a, hipStream_t s) {
     if (a.dtype == AE_BF16) IGEMM_LAUNCH_T(bf16_t, BMV, BNV, GM, GN);          \
     else IGEMM_LAUNCH_T(float, BMV, BNV, GM, GN);                              \
   } while (0)
-  if (t.bm == 256) hipLaunchKernelGGL((k_igemm<bf16_t, 256, 64, 4, 1, 64>), grid, dim3(256), 0, s, p);
+  if (t.bm == 256 && t.bn == 128) hipLaunchKernelGGL((k_igemm<bf16_t, 256, 128, 2, 2, 64>), grid, dim3(256), 0, s, p);
+  else if (t.bm == 256) hipLaunchKernelGGL((k_igemm<bf16_t, 256, 64, 4, 1, 64>), grid, dim3(256), 0, s, p);
   else if (t.bn == 128) IGEMM_LAUNCH(128, 128, 2, 2);
   else IGEMM_LAUNCH(128, 64, 2, 2);
 #undef IGEMM_LAUNCH

@@ -317,8 +317,8 @@ __global__ void k_post_bwd_reduce(const T* __restrict__ raw, const T* __restrict
 
 // one block per channel: dgamma = sum dy*xhat, dbeta = sum dy; c1 = dbeta/M, c2 = dgamma/M (batch statistics)
 __global__ void k_bn_bwd_finalize(const float* __restrict__ partial, int nblocks, double inv_rows, int C,
-                                  float* __restrict__ bn_vec, float* __restrict__ dgamma_dbeta, int batch_stats,
-                                  int stored_slots) {
+                                  float* __restrict__ bn_vec, float* __restrict__ dgamma_dbeta,
+                                  float* __restrict__ dbias, int batch_stats, int stored_slots) {
   __shared__ double sm[NT / 64 + 1];
   const int c = blockIdx.x;
   double s1 = 0.0, s2 = 0.0;
@@ -334,6 +334,10 @@ __global__ void k_bn_bwd_finalize(const float* __restrict__ partial, int nblocks
     if (stored_slots) { dgamma_dbeta[2 * C + c] = 0.0f; dgamma_dbeta[3 * C + c] = 0.0f; }
     bn_vec[4 * C + c] = batch_stats ? (float)(s1 * inv_rows) : 0.0f;
     bn_vec[5 * C + c] = batch_stats ? (float)(s2 * inv_rows) : 0.0f;
+    // gradient of the bias of the conv that feeds this batch-norm: sum over pixels of the
+    // conv-output gradient = scale*(sum dy - M*c1 - c2*sum xhat).  With batch statistics
+    // sum xhat = 0 and M*c1 = sum dy: exactly zero.  With stored statistics: scale * sum dy.
+    if (dbias) dbias[c] = batch_stats ? 0.0f : (float)((double)bn_vec[c] * s1);
   }
 }
 
@@ -376,6 +380,45 @@ __global__ void k_act_bwd(const T* __restrict__ out, const float* __restrict__ o
     float a = out_f32 ? out_f32[i] : Store<T>::ld(out + i), g = Store<T>::ld(dout + i);
     float d = act == 1 ? (a > 0.0f ? 1.0f : 0.0f) : (act == 2 ? a * (1.0f - a) : 1.0f);
     Store<T>::st(draw + i, g * d);
+  }
+}
+
+// draw = dout * act'(out) for a [rows][C] tensor, and partial[b][0][c] = column sums of draw
+// over the block's rows (the bias gradient) in the same pass
+template <typename T, int VEC>
+__global__ void k_act_bwd_colsum(const T* __restrict__ out, const float* __restrict__ out_f32,
+                                 const T* __restrict__ dout, T* __restrict__ draw, int64_t rows, int rpb, int C,
+                                 int act, float* __restrict__ partial) {
+  __shared__ float smem[NT * VEC];
+  const int groups = (C + VEC - 1) / VEC;
+  const int tpr = groups < NT ? groups : NT;
+  const int nrl = NT / tpr;
+  const int cg = threadIdx.x % tpr, rl = threadIdx.x / tpr;
+  const bool active = rl < nrl;
+  const int64_t r0 = (int64_t)blockIdx.x * rpb;
+  const int64_t r1 = r0 + rpb < rows ? r0 + rpb : rows;
+  float* pb = partial + (int64_t)blockIdx.x * 2 * C;
+  for (int cbase = 0; cbase < C; cbase += tpr * VEC) {
+    float acc[1][VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) acc[0][v] = 0.0f;
+    const int c = cbase + cg * VEC;
+    if (active && c < C) {
+      for (int64_t r = r0 + rl; r < r1; r += nrl) {
+        float a[VEC], g[VEC], d[VEC];
+        if (out_f32) load_f32<VEC>(out_f32 + r * C + c, a);
+        else load_vec<T, VEC>(out + r * C + c, a);
+        load_vec<T, VEC>(dout + r * C + c, g);
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) {
+          const float dd = act == 1 ? (a[j] > 0.0f ? 1.0f : 0.0f) : (act == 2 ? a[j] * (1.0f - a[j]) : 1.0f);
+          d[j] = round_to_storage<T>(g[j] * dd);
+          acc[0][j] += d[j];
+        }
+        store_vec<T, VEC>(draw + r * C + c, d);
+      }
+    }
+    block_col_combine<VEC, 1>(acc, cg, rl, nrl, tpr, cbase, C, pb, smem, active);
   }
 }
 
@@ -516,11 +559,10 @@ int launch_post_bwd_reduce(const void* raw, const void* dout, const float* bn_ve
   return launch_status("post_bwd_reduce");
 }
 
-int launch_bn_bwd_finalize(const float* partial, int nblocks, int64_t rows, int c, const float* gamma, float* bn_vec,
+int launch_bn_bwd_finalize(const float* partial, int nblocks, int64_t rows, int c, float* dbias, float* bn_vec,
                            float* dgamma_dbeta, int batch_stats, hipStream_t s) {
-  (void)gamma;
   hipLaunchKernelGGL(k_bn_bwd_finalize, dim3(c), dim3(NT), 0, s, partial, nblocks, 1.0 / (double)rows, c, bn_vec,
-                     dgamma_dbeta, batch_stats, batch_stats ? 0 : 1);
+                     dgamma_dbeta, dbias, batch_stats, batch_stats ? 0 : 1);
   return launch_status("bn_bwd_finalize");
 }
 
@@ -544,6 +586,15 @@ int launch_act_bwd(const void* out, const float* out_f32, const void* dout, void
   DISPATCH_T(dtype, hipLaunchKernelGGL((k_act_bwd<T>), dim3(grid_for(n_elem, NT, 16384)), dim3(NT), 0, s,
                                        (const T*)out, out_f32, (const T*)dout, (T*)draw, n_elem, act));
   return launch_status("act_bwd");
+}
+
+int launch_act_bwd_colsum(const void* out, const float* out_f32, const void* dout, void* draw, int64_t rows, int c,
+                          int act, int dtype, float* partial, hipStream_t s) {
+  const int rpb = reduce_rows_per_block(rows);
+  const int nblocks = reduce_blocks(rows);
+  DISPATCH_T_VEC(dtype, c, hipLaunchKernelGGL((k_act_bwd_colsum<T, VEC>), dim3(nblocks), dim3(NT), 0, s, (const T*)out,
+                                              out_f32, (const T*)dout, (T*)draw, rows, rpb, c, act, partial));
+  return launch_status("act_bwd_colsum");
 }
 
 int launch_colsum_finalize(const float* partial, int nblocks, int c, float* out, hipStream_t s) {

@@ -161,8 +161,10 @@ int launch_post_forward(const void* raw, const float* bn_vec, void* out, int64_t
                         int pool, int dtype, hipStream_t s);
 int launch_post_bwd_reduce(const void* raw, const void* dout, const float* bn_vec, int64_t n, int h, int w, int c,
                            int act, int pool, int dtype, float* partial, hipStream_t s);
-int launch_bn_bwd_finalize(const float* partial, int nblocks, int64_t rows, int c, const float* gamma, float* bn_vec,
+int launch_bn_bwd_finalize(const float* partial, int nblocks, int64_t rows, int c, float* dbias, float* bn_vec,
                            float* dgamma_dbeta, int batch_stats, hipStream_t s);
+int launch_act_bwd_colsum(const void* out, const float* out_f32, const void* dout, void* draw, int64_t rows, int c,
+                          int act, int dtype, float* partial, hipStream_t s);
 int launch_post_bwd_apply(const void* raw, const void* dout, const float* bn_vec, void* draw, int64_t n, int h, int w,
                           int c, int act, int pool, int has_bn, int dtype, hipStream_t s);
 int launch_act_bwd(const void* out, const float* out_f32, const void* dout, void* draw, int64_t n_elem, int act,
