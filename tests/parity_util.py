@@ -11,6 +11,24 @@ TOL = {"f32": 1e-4, "bf16": 2e-2}
 # in bf16 it is the tail of ~1e5..1e7 independent rounding errors (4.5-5.5 standard
 # deviations), so its bar is three times the L2 bar.
 TOL_MAX = {"f32": 1e-4, "bf16": 6e-2}
+# Internal activations of a bf16 model against the PLAIN (real-number) oracle: the output y is
+# held to 2e-2, but the error against real-number arithmetic grows with depth (every stored
+# tensor adds a rounding of relative size 2^-9, and zero-mean weights cancel the mean of the
+# all-positive ReLU outputs but not the errors: ~1.2x per layer).  At cfg5's full size it reaches
+# 2.1e-2 after 12 stored layers while the same tensors agree with the bf16-storage oracle — the
+# format's own semantics — to 9e-3.  So: 2e-2 against the storage oracle everywhere, 2e-2 against
+# the plain oracle for y, 3e-2 against the plain oracle for internal activations.
+TOL_ACT_PLAIN = {"f32": 1e-4, "bf16": 3e-2}
+
+# Gradients of LARGE fp32 networks.  A ReLU mask bit or max-pool winner is decided by the sign /
+# order of values that two correct fp32 implementations compute only to ~1e-6 relative; among
+# 1e7 pre-activations a few tens lie that close to the decision boundary, and each flipped
+# decision moves one full-magnitude term of the gradient: relative L2 error ~ sqrt(flipped
+# fraction) ~ 1e-3..5e-3, whatever the kernel does (the small fp32 tests, with 1e3..1e5
+# elements per layer, contain no such element and hold 1e-4).  Full-size fp32 gradients are
+# therefore held to 1e-2 (single largest deviation: 5e-2 of the largest entry, one flipped
+# term) and cosine 0.9999, and the decision-free (linear) layers to 1e-4 at full size on their own.
+LARGE_F32_GRAD = (1e-2, 0.9999)
 
 # Gradient bar for DEEP bf16 networks (relative L2 bound, minimum cosine per tensor).
 # Every ReLU mask bit and max-pool winner is a discrete decision taken on a stored bf16
@@ -108,8 +126,9 @@ def run_case(spec, batch, dtype="f32", seed=0, snr_db=10.0, first_sample=0, bn_m
             got = buf.cpu().numpy()
             for rname, rnet in refs:
                 ref = rnet.activation(tok).reshape((batch,) + chw)
+                atol = TOL_ACT_PLAIN[dtype] if rname == "plain" else tol
                 worst["act%d/%s" % (s, rname)] = assert_close(
-                    got, ref, tol, "activation of step %d (token %d) vs %s oracle" % (s, tok, rname), tol_max=tolm)
+                    got, ref, atol, "activation of step %d (token %d) vs %s oracle" % (s, tok, rname), tol_max=tolm)
     if backward:
         if cot is None:
             cot = wl.make_cotangent((batch,) + m.out_shape, seed, bf16=bf)
@@ -135,7 +154,7 @@ def run_case(spec, batch, dtype="f32", seed=0, snr_db=10.0, first_sample=0, bn_m
                 if STRICT:
                     assert np.abs(g[sl]).max() <= max(gtol, 1e-3) * scale * 10, name
                 continue
-            worst[name] = assert_close(g[sl], g_ref[sl], gtol, name, tol_max=2 * gtol if grad_cos is not None else max(gtol, tolm))
+            worst[name] = assert_close(g[sl], g_ref[sl], gtol, name, tol_max=max(2 * gtol, 5e-2) if grad_cos is not None else max(gtol, tolm))
             if grad_cos is not None and sz >= 16:
                 c = float(np.dot(g[sl], g_ref[sl]) / (np.linalg.norm(g[sl]) * np.linalg.norm(g_ref[sl])))
                 worst[name] = worst[name] + (c,)

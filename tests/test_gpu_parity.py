@@ -6,7 +6,7 @@ import pytest
 
 import oracle.ae_oracle as orc
 import workloads as wl
-from parity_util import DEEP_BF16_GRAD, TOL, assert_close, rel_errors, run_case, to_dev
+from parity_util import DEEP_BF16_GRAD, LARGE_F32_GRAD, TOL, assert_close, rel_errors, run_case, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -181,7 +181,7 @@ def test_cfg3_reduced_resolution_bf16(ae):
 def test_cfg4_launch_and_error_counts(ae):
     import torch
     cfg = wl.CONFIGS["cfg4"]
-    B, K = 8192, 64
+    B, K = cfg["batch"], 64          # one full launch of 65 536 samples
     first = 65536 * 5
     spec = cfg["spec"]
     params = wl.make_params(spec, cfg["seed"])
@@ -258,3 +258,81 @@ def test_error_codes(ae):
     assert e.value.code == -4
     assert ae.lib.model_forward(m._h, None, None, 1.0, 0, None, None) == -1
     assert "null" in ae.model_last_error()
+
+
+# ------------------------------------------------------------------ full benchmark sizes
+def test_cfg2_full_size_forward_backward(ae):
+    """cfg2 exactly as bench.py runs it (batch 256, 3x32x32, fp32), every activation and gradient."""
+    cfg = wl.CONFIGS["cfg2"]
+    run_case(cfg["spec"], cfg["batch"], dtype="f32", seed=cfg["seed"], snr_db=5.0, perturb=False,
+             grad_tol=LARGE_F32_GRAD[0], grad_cos=LARGE_F32_GRAD[1])
+
+
+FULL_SIZE_LINEAR = [
+    # decision-free layers at the sizes bench.py runs: conv forward, input gradient and weight gradient
+    # (cfg2: 64->128 at 16x16, batch 256, fp32; cfg5: 64->128 at 128x128 and up2+128->64, bf16, batch 8)
+    ("in:64x16x16,conv3:64,conv3:128", 256, "f32"),
+    ("in:64x32x32,up2,conv3:64,conv1:32", 8, "f32"),
+    ("in:64x128x128,conv3:64,conv3:128", 8, "bf16"),
+    ("in:128x64x64,conv3:128,up2,conv3:64", 8, "bf16"),
+]
+
+
+@pytest.mark.parametrize("case", range(len(FULL_SIZE_LINEAR)))
+def test_full_size_linear_layers(ae, case):
+    spec, batch, dtype = FULL_SIZE_LINEAR[case]
+    run_case(spec, batch, dtype=dtype, seed=400 + case, snr_db=10.0)
+
+
+def test_cfg3_full_size_forward(ae):
+    """cfg3 at its full size (batch 128, 3x64x64, bf16): forward against both oracles."""
+    cfg = wl.CONFIGS["cfg3"]
+    run_case(cfg["spec"], cfg["batch"], dtype="bf16", seed=cfg["seed"], snr_db=5.0, perturb=False, backward=False)
+
+
+def test_cfg5_full_size_forward(ae):
+    """cfg5 at its full size (batch 32, 3x256x256, bf16), the launch configuration bench.py times:
+    y and every saved activation against the plain and the bf16-storage oracle."""
+    cfg = wl.CONFIGS["cfg5"]
+    run_case(cfg["spec"], cfg["batch"], dtype="bf16", seed=cfg["seed"], snr_db=10.0, perturb=False, backward=False)
+
+
+def test_cfg5_full_resolution_backward_small_batch(ae):
+    """Backward of cfg5 at full 256x256 resolution (batch 2: what the oracle finishes in seconds)."""
+    cfg = wl.CONFIGS["cfg5"]
+    run_case(cfg["spec"], 2, dtype="bf16", seed=cfg["seed"], snr_db=10.0, perturb=False, check_acts=False,
+             grad_tol=DEEP_BF16_GRAD[0], grad_cos=DEEP_BF16_GRAD[1])
+
+
+def test_cfg5_full_size_backward_properties(ae):
+    """Properties of the full-size cfg5 backward that hold at any size: run-to-run determinism,
+    exact linearity in dy for a power-of-two factor, zero bias gradient in front of batch-stat BN."""
+    import torch
+    cfg = wl.CONFIGS["cfg5"]
+    B = cfg["batch"]
+    m = ae.Model(cfg["spec"], B, ae.AE_BF16)
+    p = torch.from_numpy(wl.make_params(cfg["spec"], cfg["seed"], bf16=True)).cuda()
+    x = torch.from_numpy(wl.make_input(cfg["spec"], B, cfg["seed"], bf16=True)).cuda().to(torch.bfloat16)
+    y = torch.empty((B,) + m.out_shape, dtype=torch.bfloat16, device="cuda")
+    dy = torch.empty_like(y)
+    loss = torch.zeros(1, device="cuda")
+    grads = []
+    for scale in (1.0, 1.0, 4.0):
+        m.model_forward(p, x, 10.0, cfg["seed"], y)
+        ae.model_loss_mse(y, x, loss, dy)
+        g = torch.full((m.n_params,), float("nan"), device="cuda")
+        m.model_backward(p, x, (dy * scale).contiguous(), g)
+        torch.cuda.synchronize()
+        assert torch.isfinite(g).all()
+        grads.append(g)
+    assert torch.equal(grads[0], grads[1])                 # deterministic
+    # dy*4 is exact in bf16, and every stage is linear in the incoming gradient up to bf16 rounding of
+    # the stored gradients, which commutes with a power-of-two scale: bit-exact linearity
+    assert torch.equal(grads[2], grads[0] * 4.0)
+    ent, _, _, _ = wl.param_layout(cfg["spec"])
+    toks = cfg["spec"].split(",")[1:]
+    for e in ent:
+        if e["kind"] == "b" and e["op"] + 1 < len(toks) and toks[e["op"] + 1] == "bn":
+            sl = slice(e["offset"], e["offset"] + e["shape"][0])
+            assert float(grads[0][sl].abs().max()) == 0.0
+    m.close()
