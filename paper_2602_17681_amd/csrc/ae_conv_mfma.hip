@@ -69,7 +69,42 @@ template <> __device__ __forceinline__ void mma_step<float>(const uint4v& a, con
   c = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[3], fb[3], c, 0, 0, 0);
 }
 
-template <typename T, int BM, int BN, int WGM, int WGN, int BKB>
+// Epilogue of a tile that lies wholly inside the output (no bounds checks): bias, rounding to the
+// storage type, optional column statistics of the stored value, optional ReLU, then 16-byte
+// row stores staged through this wave's LDS area.
+template <typename T, int MI, int NJ, int WN, int SW, bool STATS, bool RELU>
+__device__ __forceinline__ void igemm_store_interior(const floatx16 (&acc)[MI][NJ], const float (&bias)[NJ], T* stage,
+                                                     T* yrow, int N, int lane, float (&s1)[NJ], float (&s2)[NJ]) {
+  constexpr int ES = (int)sizeof(T);
+  constexpr int EPC = 16 / ES;               // elements per 16-byte chunk
+  constexpr int CPRO = WN / EPC;             // chunks per staged row
+  const int col_lane = lane & 31, row_lane = (lane >> 5) * 4;
+#pragma unroll
+  for (int i = 0; i < MI; ++i) {
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int lr = (e >> 2) * 8 + row_lane + (e & 3);
+        float v = acc[i][j][e] + bias[j];
+        if (STATS) { v = round_to_storage<T>(v); s1[j] += v; s2[j] = fmaf(v, v, s2[j]); }
+        if (RELU) v = fmaxf(v, 0.0f);          // rounding is monotonic and keeps 0: same as ReLU of the rounded value
+        Store<T>::st(&stage[lr * SW + j * 32 + col_lane], v);
+      }
+    }
+#pragma unroll
+    for (int c = 0; c < (32 * CPRO) / 64; ++c) {
+      const int idx = c * 64 + lane;
+      const int lr = idx / CPRO, ch = idx % CPRO;
+      *reinterpret_cast<uint4v*>(yrow + (int64_t)(i * 32 + lr) * N + ch * EPC) =
+          *reinterpret_cast<const uint4v*>(&stage[lr * SW + ch * EPC]);
+    }
+  }
+}
+
+// INTERIOR: the host guarantees M % BM == 0, N % BN == 0, 16-byte aligned rows, no sigmoid, no
+// auxiliary copy and no activation together with statistics, so the epilogue needs no checks.
+template <typename T, int BM, int BN, int WGM, int WGN, int BKB, bool INTERIOR>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k_igemm(IgemmParams p) {
   static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
   static_assert(BKB == 64 || BKB == 128, "slab row bytes");
@@ -219,39 +254,49 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   float s1[NJ], s2[NJ];
 #pragma unroll
   for (int j = 0; j < NJ; ++j) { s1[j] = 0.0f; s2[j] = 0.0f; }
+  if constexpr (INTERIOR) {
+    float bias[NJ];
 #pragma unroll
-  for (int i = 0; i < MI; ++i) {
+    for (int j = 0; j < NJ; ++j) bias[j] = p.bias ? p.bias[n0 + wn * WN + j * 32 + col_lane] : 0.0f;
+    T* yrow = Y + (m0 + wm * WM) * p.N + n0 + wn * WN;
+    if (p.partial) igemm_store_interior<T, MI, NJ, WN, SW, true, false>(acc, bias, stage, yrow, p.N, lane, s1, s2);
+    else if (p.act == ACT_RELU) igemm_store_interior<T, MI, NJ, WN, SW, false, true>(acc, bias, stage, yrow, p.N, lane, s1, s2);
+    else igemm_store_interior<T, MI, NJ, WN, SW, false, false>(acc, bias, stage, yrow, p.N, lane, s1, s2);
+  } else {
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) {
-      const int col = n0 + wn * WN + j * 32 + col_lane;
-      const bool col_ok = col < p.N;
-      const float bias = (p.bias && col_ok) ? p.bias[col] : 0.0f;
+    for (int i = 0; i < MI; ++i) {
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int lr = (e >> 2) * 8 + row_lane + (e & 3);
-        const int64_t m = m0 + wm * WM + i * 32 + lr;
-        const float v = round_to_storage<T>(acc[i][j][e] + bias);   // the stored conv result
-        if (p.partial && m < p.M && col_ok) { s1[j] += v; s2[j] = fmaf(v, v, s2[j]); }
-        const float a = apply_act(v, p.act);
-        if (wide_store) {
-          Store<T>::st(&stage[lr * SW + j * 32 + col_lane], a);
-        } else if (m < p.M && col_ok) {
-          Store<T>::st(&Y[m * p.N + col], a);
-          if (p.y_aux) p.y_aux[m * p.N + col] = a;
+      for (int j = 0; j < NJ; ++j) {
+        const int col = n0 + wn * WN + j * 32 + col_lane;
+        const bool col_ok = col < p.N;
+        const float bias = (p.bias && col_ok) ? p.bias[col] : 0.0f;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int lr = (e >> 2) * 8 + row_lane + (e & 3);
+          const int64_t m = m0 + wm * WM + i * 32 + lr;
+          const float v = round_to_storage<T>(acc[i][j][e] + bias);   // the stored conv result
+          if (p.partial && m < p.M && col_ok) { s1[j] += v; s2[j] = fmaf(v, v, s2[j]); }
+          const float a = apply_act(v, p.act);
+          if (wide_store) {
+            Store<T>::st(&stage[lr * SW + j * 32 + col_lane], a);
+          } else if (m < p.M && col_ok) {
+            Store<T>::st(&Y[m * p.N + col], a);
+            if (p.y_aux) p.y_aux[m * p.N + col] = a;
+          }
         }
       }
-    }
-    if (wide_store) {
-      constexpr int EPC = 16 / ES;               // elements per 16-byte chunk
-      constexpr int CPRO = WN / EPC;             // chunks per staged row
+      if (wide_store) {
+        constexpr int EPC = 16 / ES;               // elements per 16-byte chunk
+        constexpr int CPRO = WN / EPC;             // chunks per staged row
 #pragma unroll
-      for (int c = 0; c < (32 * CPRO) / 64; ++c) {
-        const int idx = c * 64 + lane;
-        const int lr = idx / CPRO, ch = idx % CPRO;
-        const int64_t m = m0 + wm * WM + i * 32 + lr;
-        const int col0 = n0 + wn * WN + ch * EPC;
-        if (m < p.M && col0 < p.N)
-          *reinterpret_cast<uint4v*>(Y + m * p.N + col0) = *reinterpret_cast<const uint4v*>(&stage[lr * SW + ch * EPC]);
+        for (int c = 0; c < (32 * CPRO) / 64; ++c) {
+          const int idx = c * 64 + lane;
+          const int lr = idx / CPRO, ch = idx % CPRO;
+          const int64_t m = m0 + wm * WM + i * 32 + lr;
+          const int col0 = n0 + wn * WN + ch * EPC;
+          if (m < p.M && col0 < p.N)
+            *reinterpret_cast<uint4v*>(Y + m * p.N + col0) = *reinterpret_cast<const uint4v*>(&stage[lr * SW + ch * EPC]);
+        }
       }
     }
   }
@@ -322,20 +367,28 @@ int launch_conv_mfma(const ConvArgs& a, hipStream_t s) {
   p.tiles_n = (a.cout + t.bn - 1) / t.bn;
   const int64_t tiles_m = (p.M + t.bm - 1) / t.bm;
   dim3 grid((unsigned)(tiles_m * p.tiles_n));
+  const bool interior = p.M % t.bm == 0 && p.N % t.bn == 0 && !a.y_aux && a.act != ACT_SIGMOID &&
+                        !(a.partial && a.act != ACT_NONE);
+#define IGEMM_LAUNCH_K(T, BMV, BNV, GM, GN, KB)                                                        \
+  do {                                                                                                 \
+    if (interior) hipLaunchKernelGGL((k_igemm<T, BMV, BNV, GM, GN, KB, true>), grid, dim3(256), 0, s, p); \
+    else hipLaunchKernelGGL((k_igemm<T, BMV, BNV, GM, GN, KB, false>), grid, dim3(256), 0, s, p);      \
+  } while (0)
 #define IGEMM_LAUNCH_T(T, BMV, BNV, GM, GN)                                                            \
   do {                                                                                                 \
-    if (t.bkb == 128) hipLaunchKernelGGL((k_igemm<T, BMV, BNV, GM, GN, 128>), grid, dim3(256), 0, s, p); \
-    else hipLaunchKernelGGL((k_igemm<T, BMV, BNV, GM, GN, 64>), grid, dim3(256), 0, s, p);             \
+    if (t.bkb == 128) IGEMM_LAUNCH_K(T, BMV, BNV, GM, GN, 128);                                        \
+    else IGEMM_LAUNCH_K(T, BMV, BNV, GM, GN, 64);                                                      \
   } while (0)
 #define IGEMM_LAUNCH(BMV, BNV, GM, GN)                                         \
   do {                                                                         \
     if (a.dtype == AE_BF16) IGEMM_LAUNCH_T(bf16_t, BMV, BNV, GM, GN);          \
     else IGEMM_LAUNCH_T(float, BMV, BNV, GM, GN);                              \
   } while (0)
-  if (t.bm == 256 && t.bn == 128) hipLaunchKernelGGL((k_igemm<bf16_t, 256, 128, 2, 2, 64>), grid, dim3(256), 0, s, p);
-  else if (t.bm == 256) hipLaunchKernelGGL((k_igemm<bf16_t, 256, 64, 4, 1, 64>), grid, dim3(256), 0, s, p);
+  if (t.bm == 256 && t.bn == 128) IGEMM_LAUNCH_K(bf16_t, 256, 128, 2, 2, 64);
+  else if (t.bm == 256) IGEMM_LAUNCH_K(bf16_t, 256, 64, 4, 1, 64);
   else if (t.bn == 128) IGEMM_LAUNCH(128, 128, 2, 2);
   else IGEMM_LAUNCH(128, 64, 2, 2);
+#undef IGEMM_LAUNCH_K
 #undef IGEMM_LAUNCH
 #undef IGEMM_LAUNCH_T
   return launch_status("conv_mfma");
