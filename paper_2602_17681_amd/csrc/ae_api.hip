@@ -138,8 +138,8 @@ int forward_conv(ae_model* m, int si, Step& st, const float* params, const void*
       nblk = thin_in_mfma_blocks(P.batch, st.hc, st.wc);
     }
     TIMED(si, "fwd.conv_thin_in_mfma", conv_flops, conv_bytes,
-          launch_thin_in_mfma(in, params + st.w_off, a.bias, a.y, a.partial, P.batch, st.hc, st.wc, st.cin, st.cout, 0,
-                              a.act, s));
+          launch_thin_in_mfma(in, params + st.w_off, st.wpack, a.bias, a.y, a.partial, P.batch, st.hc, st.wc, st.cin,
+                              st.cout, 0, a.act, 0, s));
   } else if (st.thin == 1) {
     if (st.has_bn && P.bn_mode == 0) {
       a.partial = m->partial;
@@ -222,22 +222,29 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
     TIMED(si, "bwd.bias_planesum", 0.0, raw_el * es,
           launch_plane_sums(dr, P.batch, st.cout, (int64_t)st.hc * st.wc, P.dtype, m->partial, s));
     TIMED(si, "bwd.bias_finalize", 0.0, 0.0, launch_colsum_finalize(m->partial, P.batch, st.cout, grads + st.b_off, s));
-    TIMED(si, "bwd.wgrad_thin", conv_flops, (in_el + raw_el) * es + wel * 4,
-          launch_thin_wgrad(dr, in, m->wgrad_ws, grads + st.w_off, P.batch, st.hin, st.win, st.cout, st.cin, 1, st.up,
-                            P.dtype, s));
+    if (thin_wgrad_mfma_supported(st.cout, st.cin, st.win, P.dtype))
+      TIMED(si, "bwd.wgrad_thin_mfma", conv_flops, (in_el + raw_el) * es + wel * 4,
+            launch_thin_wgrad_mfma(dr, in, m->wgrad_ws, grads + st.w_off, P.batch, st.hin, st.win, st.cout, st.cin, 1,
+                                   st.up, s));
+    else
+      TIMED(si, "bwd.wgrad_thin", conv_flops, (in_el + raw_el) * es + wel * 4,
+            launch_thin_wgrad(dr, in, m->wgrad_ws, grads + st.w_off, P.batch, st.hin, st.win, st.cout, st.cin, 1, st.up,
+                              P.dtype, s));
     if (st.needs_dx) {
       const double full_el = (double)rows * st.cin;
-      if (thin_in_mfma_supported(st.cout, st.cin, st.k, 0, P.dtype))
-        TIMED(si, "bwd.dgrad_thin_mfma", conv_flops, (raw_el + full_el) * es,
-              launch_thin_in_mfma(dr, params + st.w_off, nullptr, st.up ? m->dfull : gnext, nullptr, P.batch, st.hc,
-                                  st.wc, st.cout, st.cin, 1, ACT_NONE, s));
-      else
+      if (thin_in_mfma_supported(st.cout, st.cin, st.k, 0, P.dtype)) {
+        // the 2x2 sum that undoes the upsample happens in the kernel's epilogue
+        TIMED(si, "bwd.dgrad_thin_mfma", conv_flops, (raw_el + in_el) * es,
+              launch_thin_in_mfma(dr, params + st.w_off, st.wpack_d, nullptr, gnext, nullptr, P.batch, st.hc, st.wc,
+                                  st.cout, st.cin, 1, ACT_NONE, st.up, s));
+      } else {
         TIMED(si, "bwd.dgrad_thin", conv_flops, (raw_el + full_el) * es,
               launch_thin_in_conv(dr, params + st.w_off, nullptr, st.up ? m->dfull : gnext, nullptr, P.batch, st.hc,
                                   st.wc, st.cout, st.cin, 1, ACT_NONE, P.dtype, s));
-      if (st.up)
-        TIMED(si, "bwd.upsum", 0.0, (full_el + in_el) * es,
-              launch_upsum(m->dfull, gnext, P.batch, st.hin, st.win, st.cin, P.dtype, s));
+        if (st.up)
+          TIMED(si, "bwd.upsum", 0.0, (full_el + in_el) * es,
+                launch_upsum(m->dfull, gnext, P.batch, st.hin, st.win, st.cin, P.dtype, s));
+      }
     }
     return AE_OK;
   }
@@ -250,7 +257,7 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
   if (st.thin == 1) {
     if (thin_wgrad_mfma_supported(st.cin, st.cout, st.wc, P.dtype))
       TIMED(si, "bwd.wgrad_thin_mfma", conv_flops, (in_el + raw_el) * es + wel * 4,
-            launch_thin_wgrad_mfma(in, dr, m->wgrad_ws, grads + st.w_off, P.batch, st.hc, st.wc, st.cin, st.cout, s));
+            launch_thin_wgrad_mfma(in, dr, m->wgrad_ws, grads + st.w_off, P.batch, st.hc, st.wc, st.cin, st.cout, 0, 0, s));
     else
       TIMED(si, "bwd.wgrad_thin", conv_flops, (in_el + raw_el) * es + wel * 4,
             launch_thin_wgrad(in, dr, m->wgrad_ws, grads + st.w_off, P.batch, st.hc, st.wc, st.cin, st.cout, 0, 0,

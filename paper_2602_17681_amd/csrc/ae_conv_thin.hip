@@ -327,360 +327,6 @@ __global__ void k_plane_sums(const T* __restrict__ x, int C, int64_t HW, float* 
   if (threadIdx.x == 0) { partial[(n * 2) * C + c] = s1; partial[(n * 2 + 1) * C + c] = s2; }
 }
 
-// ---------------------------------------------------------------------------
-// thin-in conv on the matrix cores (bf16).  A workgroup owns a TH x TW patch of one
-// image (TH*TW = 256 pixels).  The patch plus its halo is copied from the planar
-// input into LDS as interleaved pixels of 4 channels (8 bytes, channel 3 = 0).  For
-// one filter row r the three taps of a pixel are then 12 consecutive bf16 values —
-// one K = 16 MFMA step (the last four weights are zero):
-//   k = 4*s + ci,  A[pixel][k] = tile[h+r][w+s][ci],  B[k][co] = Wk[co][ci][r][s].
-// Three MFMA steps (r = 0,1,2) per 32 pixels x 32 channels; the weights stay in
-// registers for the whole kernel.  Epilogue as in the implicit-GEMM kernel.
-// ---------------------------------------------------------------------------
-typedef __bf16 t_bf16x8 __attribute__((ext_vector_type(8)));
-typedef float t_floatx16 __attribute__((ext_vector_type(16)));
-
-template <int NJ>
-__global__ __launch_bounds__(NT) void k_thin_in_mfma(const bf16_t* __restrict__ thin, const float* __restrict__ wcanon,
-                                                     const float* __restrict__ bias, bf16_t* __restrict__ out,
-                                                     float* __restrict__ partial, int n_img, int H, int W, int CT,
-                                                     int CW, int flip, int act, int TW, int tw_shift, int ntiles) {
-  constexpr int MAXT = 408;                     // (TH+2)*(TW+4) cells for every TW in {8,...,64}
-  constexpr int SW = NJ * 32 + 8;               // staging row stride of the epilogue
-  __shared__ __attribute__((aligned(16))) bf16_t tile[MAXT * 4];   // [(TH+2)][(TW+4)][4]
-  __shared__ __attribute__((aligned(16))) bf16_t swt[NJ * 32 * 3 * 16];  // [co][r][16]
-  __shared__ __attribute__((aligned(16))) bf16_t stage_all[4 * 32 * SW];
-  __shared__ float sRed[4][2][NJ * 32];
-  const int TH = NT >> tw_shift;
-  const int PW = TW + 4;                        // padded tile width (col 0 is w0-1)
-  const int tiles_w = (W + TW - 1) / TW, tiles_h = (H + TH - 1) / TH;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int64_t HW = (int64_t)H * W;
-
-  // weights -> LDS as bf16 [co][r][k], k = 4*s + ci (zero where ci >= CT or s == 3); once per workgroup
-  for (int i = tid; i < NJ * 32 * 48; i += NT) {
-    const int k = i & 15, r = (i >> 4) % 3, co = i / 48;
-    const int s_ = k >> 2, ci = k & 3;
-    float v = 0.0f;
-    if (co < CW && ci < CT && s_ < 3)
-      v = flip ? wcanon[(((int64_t)ci * CW + co) * 3 + (2 - r)) * 3 + (2 - s_)]
-               : wcanon[(((int64_t)co * CT + ci) * 3 + r) * 3 + s_];
-    swt[i] = f32_to_bf16(v);
-  }
-  __syncthreads();
-  const int frag_row = lane & 31, g = lane >> 5;
-  t_bf16x8 bfrag[3][NJ];
-#pragma unroll
-  for (int r = 0; r < 3; ++r)
-#pragma unroll
-    for (int j = 0; j < NJ; ++j)
-      bfrag[r][j] = *reinterpret_cast<const t_bf16x8*>(&swt[((j * 32 + frag_row) * 3 + r) * 16 + g * 8]);
-  const int col_lane = lane & 31, row_lane = (lane >> 5) * 4;
-  float bs[NJ];
-#pragma unroll
-  for (int j = 0; j < NJ; ++j) bs[j] = (bias && j * 32 + col_lane < CW) ? bias[j * 32 + col_lane] : 0.0f;
-  bf16_t* stage = stage_all + wave * (32 * SW);
-
-  for (int t = blockIdx.x; t < ntiles; t += gridDim.x) {
-    int b = t;
-    const int tx = b % tiles_w; b /= tiles_w;
-    const int ty = b % tiles_h;
-    const int n = b / tiles_h;
-    const int h0 = ty * TH, w0 = tx * TW;
-    __syncthreads();                            // the previous patch and its statistics are consumed
-    // input patch -> LDS (clamped, unconditional loads; zero outside the image and in the padding channel)
-    const int cells = (TH + 2) * PW;
-    for (int i = tid; i < cells * 4; i += NT) {
-      const int ci = i & 3, cell = i >> 2;
-      const int pc = cell % PW, pr = cell / PW;
-      const int hh = h0 + pr - 1, ww = w0 + pc - 1;
-      const bool ok = ci < CT && hh >= 0 && hh < H && ww >= 0 && ww < W;
-      const bf16_t v = thin[((int64_t)n * CT + (ci < CT ? ci : 0)) * HW + (int64_t)min(max(hh, 0), H - 1) * W + min(max(ww, 0), W - 1)];
-      tile[i] = ok ? v : (bf16_t)0;
-    }
-    __syncthreads();
-
-    t_floatx16 acc[2][NJ];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int j = 0; j < NJ; ++j)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int pt = wave * 64 + i * 32 + frag_row;     // this lane's pixel of the patch
-      const int th = pt >> tw_shift, tw = pt & (TW - 1);
-#pragma unroll
-      for (int r = 0; r < 3; ++r) {
-        // k-chunk g: pixels (tw + 2g, tw + 2g + 1) of padded row th + r, 4 channels each = 16 bytes
-        const bf16_t* src = &tile[((th + r) * PW + tw + 2 * g) * 4];
-        union { uint2 u[2]; t_bf16x8 v; } a;
-        a.u[0] = *reinterpret_cast<const uint2*>(src);
-        a.u[1] = *reinterpret_cast<const uint2*>(src + 4);
-#pragma unroll
-        for (int j = 0; j < NJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, bfrag[r][j], acc[i][j], 0, 0, 0);
-      }
-    }
-
-    // epilogue: element e of lane l in tile (i,j): patch pixel wave*64 + i*32 + (e/4)*8 + (l/32)*4 + e%4,
-    // channel j*32 + l%32.  Staged through wave-private LDS so that global stores are 16 bytes wide.
-    float s1[NJ], s2[NJ];
-#pragma unroll
-    for (int j = 0; j < NJ; ++j) { s1[j] = 0.0f; s2[j] = 0.0f; }
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-#pragma unroll
-      for (int j = 0; j < NJ; ++j) {
-        const int col = j * 32 + col_lane;
-        const bool col_ok = col < CW;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int lr = (e >> 2) * 8 + row_lane + (e & 3);
-          const int pt = wave * 64 + i * 32 + lr;
-          const int hh = h0 + (pt >> tw_shift), ww = w0 + (pt & (TW - 1));
-          const float v = bf16_to_f32(f32_to_bf16(acc[i][j][e] + bs[j]));
-          if (partial && col_ok && hh < H && ww < W) { s1[j] += v; s2[j] = fmaf(v, v, s2[j]); }
-          stage[lr * SW + col] = f32_to_bf16(apply_act(v, act));
-        }
-      }
-      constexpr int CPR = NJ * 4;                // 16-byte chunks per pixel row
-#pragma unroll
-      for (int c = 0; c < (32 * CPR) / 64; ++c) {
-        const int idx = c * 64 + lane;
-        const int lr = idx / CPR, ch = idx % CPR;
-        const int pt = wave * 64 + i * 32 + lr;
-        const int hh = h0 + (pt >> tw_shift), ww = w0 + (pt & (TW - 1));
-        if (hh < H && ww < W && ch * 8 < CW)
-          *reinterpret_cast<uint4*>(out + (((int64_t)n * H + hh) * W + ww) * CW + ch * 8) =
-              *reinterpret_cast<const uint4*>(&stage[lr * SW + ch * 8]);
-      }
-    }
-    if (partial) {
-#pragma unroll
-      for (int j = 0; j < NJ; ++j) {
-        const float t1 = s1[j] + __shfl_xor(s1[j], 32, 64);
-        const float t2 = s2[j] + __shfl_xor(s2[j], 32, 64);
-        if (lane < 32) { sRed[wave][0][j * 32 + col_lane] = t1; sRed[wave][1][j * 32 + col_lane] = t2; }
-      }
-      __syncthreads();
-      for (int i = tid; i < 2 * NJ * 32; i += NT) {
-        const int q = i / (NJ * 32), c = i % (NJ * 32);
-        if (c < CW) partial[((int64_t)t * 2 + q) * CW + c] = sRed[0][q][c] + sRed[1][q][c] + sRed[2][q][c] + sRed[3][q][c];
-      }
-    }
-  }
-}
-
-// ---------------------------------------------------------------------------
-// Weight gradient of the first layer on the matrix cores (bf16):
-//   dW[cw][ci][r][s] = sum over pixels q of dY[q][cw] * x[n][ci][h+r-1][w+s-1].
-// Same patch layout as k_thin_in_mfma: for filter row r the 12 values (s,ci) of pixel q are
-// contiguous in the LDS patch, and the next pixel starts 4 elements later.  So with
-// k = 16*r + 4*s + ci, B[q][k] is a strided view of the patch, and
-//   D[cw][k] = sum_q A[cw][q] * B[q][k],  A = dY^T
-// is an MFMA with the pixel as the reduction index; both operands are pixel-major in LDS and
-// are read with the transposing LDS load.  A workgroup walks over patches (persistent),
-// each wave owning 64 pixels of a patch, and accumulates in registers; at the end the four
-// waves are summed through LDS in a fixed order and one partial [cw][64] is written.
-// ---------------------------------------------------------------------------
-typedef short t_short4 __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) t_short4 t_lds_short4;
-
-__device__ __forceinline__ t_bf16x8 thin_tr_frag(const bf16_t* p0, const bf16_t* p1) {
-  t_short4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((t_lds_short4*)p0);
-  t_short4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((t_lds_short4*)p1);
-  union { short s[8]; t_bf16x8 v; } u;
-  u.s[0] = lo[0]; u.s[1] = lo[1]; u.s[2] = lo[2]; u.s[3] = lo[3];
-  u.s[4] = hi[0]; u.s[5] = hi[1]; u.s[6] = hi[2]; u.s[7] = hi[3];
-  return u.v;
-}
-
-template <int MI>   // CW = 32*MI wide channels
-__global__ __launch_bounds__(NT) void k_thin_wgrad_mfma(const bf16_t* __restrict__ thin, const bf16_t* __restrict__ wide,
-                                                        float* __restrict__ partial, int n_img, int H, int W, int CT,
-                                                        int TW, int tw_shift, int ntiles) {
-  constexpr int CW = 32 * MI;
-  constexpr int LA = CW + 16;
-  constexpr int MAXT = 408;                     // (TH+2)*(TW+4) cells for every TW in {16,32,64}
-  __shared__ __attribute__((aligned(16))) bf16_t tile[MAXT * 4];
-  __shared__ __attribute__((aligned(16))) bf16_t sW[NT * LA];
-  const int TH = NT >> tw_shift;
-  const int PW = TW + 4;
-  const int tiles_w = (W + TW - 1) / TW, tiles_h = (H + TH - 1) / TH;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int64_t HW = (int64_t)H * W;
-  const int grp = lane >> 4, sl = lane & 15;
-
-  t_floatx16 acc[MI][2];
-#pragma unroll
-  for (int i = 0; i < MI; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
-
-  for (int t = blockIdx.x; t < ntiles; t += gridDim.x) {
-    int b = t;
-    const int tx = b % tiles_w; b /= tiles_w;
-    const int ty = b % tiles_h;
-    const int n = b / tiles_h;
-    const int h0 = ty * TH, w0 = tx * TW;
-    __syncthreads();                            // previous patch fully consumed
-    const int cells = (TH + 2) * PW;
-    for (int i = tid; i < cells * 4; i += NT) {
-      const int ci = i & 3, cell = i >> 2;
-      const int pc = cell % PW, pr = cell / PW;
-      const int hh = h0 + pr - 1, ww = w0 + pc - 1;
-      const bool ok = ci < CT && hh >= 0 && hh < H && ww >= 0 && ww < W;
-      const bf16_t v = thin[((int64_t)n * CT + (ci < CT ? ci : 0)) * HW + (int64_t)min(max(hh, 0), H - 1) * W + min(max(ww, 0), W - 1)];
-      tile[i] = ok ? v : (bf16_t)0;
-    }
-    // dY slab: patch pixel p = th*TW + tw -> row p of sW
-    constexpr int CPP = CW / 8;                 // 16-byte chunks per pixel
-#pragma unroll
-    for (int c = 0; c < CPP; ++c) {
-      const int idx = c * NT + tid;
-      const int p = idx / CPP, ch = idx % CPP;
-      const int hh = h0 + (p >> tw_shift), ww = w0 + (p & (TW - 1));
-      const bool ok = hh < H && ww < W;
-      uint4 v = *reinterpret_cast<const uint4*>(wide + (((int64_t)n * H + min(hh, H - 1)) * W + min(ww, W - 1)) * CW + ch * 8);
-      if (!ok) { v.x = 0u; v.y = 0u; v.z = 0u; v.w = 0u; }
-      *reinterpret_cast<uint4*>(&sW[p * LA + ch * 8]) = v;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      const int p0 = wave * 64 + ks * 16;       // 16 consecutive pixels of one patch row
-      const int th = p0 >> tw_shift, tw0 = p0 & (TW - 1);
-      const int psub = 8 * (grp >> 1) + (sl >> 2);
-      t_bf16x8 a[MI], bfr[2];
-#pragma unroll
-      for (int i = 0; i < MI; ++i) {
-        const bf16_t* q = &sW[(p0 + psub) * LA + i * 32 + 16 * (grp & 1) + 4 * (sl & 3)];
-        a[i] = thin_tr_frag(q, q + 4 * LA);
-      }
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int r = min(2 * j + (grp & 1), 2);  // columns 48..63 are unused: any finite data
-        const bf16_t* q = &tile[((th + r) * PW + tw0 + psub) * 4 + 4 * (sl & 3)];
-        bfr[j] = thin_tr_frag(q, q + 16);
-      }
-#pragma unroll
-      for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bfr[j], acc[i][j], 0, 0, 0);
-    }
-  }
-  // sum the four waves in a fixed order through LDS (reusing the slab), then write [cw][64]
-  float* sF = reinterpret_cast<float*>(sW);     // MI*2*1024 floats <= NT*LA*2 bytes
-  for (int wv = 0; wv < 4; ++wv) {
-    __syncthreads();
-    if (wave == wv) {
-#pragma unroll
-      for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const int row = i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3), col = j * 32 + (lane & 31);
-            if (wv == 0) sF[row * 64 + col] = acc[i][j][e];
-            else sF[row * 64 + col] += acc[i][j][e];
-          }
-    }
-  }
-  __syncthreads();
-  for (int i = tid; i < CW * 64; i += NT) partial[(int64_t)blockIdx.x * CW * 64 + i] = sF[i];
-}
-
-// dW[cw][ct][r][s] = sum over blocks of partial[b][cw][16*r + 4*s + ct]
-__global__ void k_thin_wgrad_mfma_reduce(const float* __restrict__ partial, int nblocks, int CW, int CT,
-                                         float* __restrict__ dw) {
-  const int total = CW * CT * 9;
-  for (int i = blockIdx.x * NT + threadIdx.x; i < total; i += gridDim.x * NT) {
-    const int tap = i % 9, ct = (i / 9) % CT, cw = i / (9 * CT);
-    const int r = tap / 3, s = tap % 3;
-    float acc = 0.0f;
-    for (int b = 0; b < nblocks; ++b) acc += partial[((int64_t)b * CW + cw) * 64 + 16 * r + 4 * s + ct];
-    dw[i] = acc;
-  }
-}
-
-struct ThinTile { int tw, shift, blocks; };
-ThinTile thin_tile(int n, int h, int w) {
-  int tw = 8, shift = 3;
-  while (tw < 64 && tw < w) { tw <<= 1; ++shift; }
-  const int th = NT / tw;
-  ThinTile t;
-  t.tw = tw; t.shift = shift;
-  t.blocks = n * ((h + th - 1) / th) * ((w + tw - 1) / tw);
-  return t;
-}
-
-}  // namespace
-
-bool thin_in_mfma_supported(int ct, int cw, int k, int up, int dtype) {
-  return dtype == AE_BF16 && k == 3 && !up && ct >= 1 && ct <= 4 && cw % 32 == 0 && cw <= 128;
-}
-
-int thin_in_mfma_blocks(int n, int h, int w) { return thin_tile(n, h, w).blocks; }
-
-int launch_thin_in_mfma(const void* thin, const float* wcanon, const float* bias, void* out, float* partial, int n,
-                        int h, int w, int ct, int cw, int flip, int act, hipStream_t s) {
-  if (!thin_in_mfma_supported(ct, cw, 3, 0, AE_BF16)) return fail(AE_EINVAL, "thin_in_mfma: shape not supported");
-  const ThinTile t = thin_tile(n, h, w);
-  const int nj = cw / 32;
-#define LAUNCH_TIM(NJV)                                                                                          \
-  hipLaunchKernelGGL((k_thin_in_mfma<NJV>), dim3((unsigned)t.blocks), dim3(NT), 0, s,                                   \
-                     (const bf16_t*)thin, wcanon, bias, (bf16_t*)out, partial, n, h, w, ct, cw, flip, act, t.tw, t.shift, \
-                     t.blocks)
-  switch (nj) {
-    case 1: LAUNCH_TIM(1); break;
-    case 2: LAUNCH_TIM(2); break;
-    case 3: LAUNCH_TIM(3); break;
-    default: LAUNCH_TIM(4); break;
-  }
-#undef LAUNCH_TIM
-  return launch_status("thin_in_mfma");
-}
-
-bool thin_wgrad_mfma_supported(int ct, int cw, int w, int dtype) {
-  return dtype == AE_BF16 && ct >= 1 && ct <= 4 && cw % 32 == 0 && cw <= 128 && w >= 16;
-}
-
-int thin_wgrad_mfma_blocks(int n, int h, int w) {
-  const int tiles = thin_tile(n, h, w).blocks;
-  return tiles < 768 ? tiles : 768;             // three persistent workgroups per compute unit
-}
-
-int64_t thin_wgrad_mfma_workspace_floats(int n, int h, int w, int cw) {
-  return (int64_t)thin_wgrad_mfma_blocks(n, h, w) * cw * 64;
-}
-
-// first-layer weight gradient: thin = planar input [n][ct][h][w], wide = output gradient [n*h*w][cw]
-int launch_thin_wgrad_mfma(const void* thin, const void* wide, float* workspace, float* dw_canonical, int n, int h,
-                           int w, int ct, int cw, hipStream_t s) {
-  if (!thin_wgrad_mfma_supported(ct, cw, w, AE_BF16)) return fail(AE_EINVAL, "thin_wgrad_mfma: shape not supported");
-  const ThinTile t = thin_tile(n, h, w);
-  const int nblk = thin_wgrad_mfma_blocks(n, h, w);
-#define LAUNCH_TWM(MIV)                                                                                         \
-  hipLaunchKernelGGL((k_thin_wgrad_mfma<MIV>), dim3((unsigned)nblk), dim3(NT), 0, s, (const bf16_t*)thin,        \
-                     (const bf16_t*)wide, workspace, n, h, w, ct, t.tw, t.shift, t.blocks)
-  switch (cw / 32) {
-    case 1: LAUNCH_TWM(1); break;
-    case 2: LAUNCH_TWM(2); break;
-    case 3: LAUNCH_TWM(3); break;
-    default: LAUNCH_TWM(4); break;
-  }
-#undef LAUNCH_TWM
-  AE_TRY(launch_status("thin_wgrad_mfma"));
-  const int total = cw * ct * 9;
-  hipLaunchKernelGGL(k_thin_wgrad_mfma_reduce, dim3((unsigned)((total + NT - 1) / NT)), dim3(NT), 0, s, workspace, nblk,
-                     cw, ct, dw_canonical);
-  return launch_status("thin_wgrad_mfma_reduce");
-}
-
-namespace {
 }  // namespace
 
 bool thin_in_supported(int ct, int cw, int k, int up) {

@@ -1,0 +1,542 @@
+// ae_conv_thin_mfma.hip — bf16 matrix-core kernels for the 3x3 convolutions with a
+// "thin" side (1..4 channels): the first and the last layer of the autoencoders.
+//
+//   thin-in conv  : out[q][cw] = b[cw] + sum_{ct,r,s} thin[n][ct][h+r-1][w+s-1] * Wk[cw][ct][r][s]
+//                   forward of the first layer; input gradient of the last layer (flipped
+//                   weights), optionally summed over 2x2 pixel groups (the backward of the
+//                   x2 upsample the last conv reads through).
+//   thin wgrad    : dW = sum over wide pixels q of wide[q][cw] * G(q)[tap][ct]
+//                   weight gradient of the first layer (G gathered from the layer input)
+//                   and of the last layer (G gathered from the output gradient).
+//
+// The thin tensor is planar [n][ct][H][W] (the layout of the library's boundary); the wide
+// tensor is [pixels][cw].  All kernels work on a patch of the thin tensor held in LDS as
+// pixels of 4 interleaved channels (8 bytes): the three taps (s = 0,1,2) of one filter row
+// of a pixel are then 12 consecutive values, i.e. one K = 16 MFMA step with
+//   k = 4*s + ci   (s = 3 and ci >= CT carry zero weights / are ignored).
+// These layers are bound by HBM (the wide tensor) — the kernels issue all their global loads
+// of a patch at once, and never loop over dependent loads.
+#include "ae_device.h"
+#include "ae_internal.h"
+
+namespace ae {
+namespace {
+
+constexpr int NT = 256;
+typedef __bf16 t_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float t_floatx16 __attribute__((ext_vector_type(16)));
+typedef short t_short4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) t_short4 t_lds_short4;
+
+// ---------------------------------------------------------------------------
+// LDS patch of one sample's planar thin tensor img[CT][H][W].
+// Cell (pr, pc), pr < rows, pc < IW + 4, holds pixel (h_first + pr, w_first - 2 + pc):
+// pc = 1 is the left halo column, pc = 2 .. IW+1 the interior (IW a multiple of 8,
+// w_first a multiple of 8), pc = IW+2 the right halo, pc = 0 and IW+3 are zero.
+// Pixels outside the image and channels >= CT are zero.
+// vec: W % 8 == 0 and img 16-byte aligned — the interior moves as 16-byte loads.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void thin_fill_patch(bf16_t* __restrict__ tile, const bf16_t* __restrict__ img, int H, int W,
+                                                int CT, int h_first, int w_first, int rows, int IW, bool vec) {
+  const int PW = IW + 4;
+  const int tid = threadIdx.x;
+  const int64_t HW = (int64_t)H * W;
+  if (vec) {
+    const int cpr = IW >> 3;
+    for (int idx = tid; idx < rows * cpr; idx += NT) {
+      const int pr = idx / cpr, c = idx - pr * cpr;
+      const int hh = h_first + pr, ww = w_first + 8 * c;
+      const bool ok = hh >= 0 && hh < H && ww < W;
+      const int64_t off = (int64_t)min(max(hh, 0), H - 1) * W + min(ww, W - 8);
+      uint32_t v[4][4];
+#pragma unroll
+      for (int ci = 0; ci < 4; ++ci) {
+        const uint4 t = *reinterpret_cast<const uint4*>(img + (int64_t)min(ci, CT - 1) * HW + off);
+        const bool keep = ok && ci < CT;
+        v[ci][0] = keep ? t.x : 0u; v[ci][1] = keep ? t.y : 0u; v[ci][2] = keep ? t.z : 0u; v[ci][3] = keep ? t.w : 0u;
+      }
+      bf16_t* dst = tile + ((int64_t)pr * PW + 2 + 8 * c) * 4;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {              // word k holds pixels 2k (low half) and 2k+1 (high half)
+        uint4 o;
+        o.x = (v[0][k] & 0xFFFFu) | (v[1][k] << 16);
+        o.y = (v[2][k] & 0xFFFFu) | (v[3][k] << 16);
+        o.z = (v[0][k] >> 16) | (v[1][k] & 0xFFFF0000u);
+        o.w = (v[2][k] >> 16) | (v[3][k] & 0xFFFF0000u);
+        *reinterpret_cast<uint4*>(dst + 8 * k) = o;
+      }
+    }
+    // halo columns (and the two zero columns), by the high threads so that they overlap the interior
+    for (int idx = NT - 1 - tid; idx < rows * 2; idx += NT) {
+      const int pr = idx >> 1, side = idx & 1;
+      const int hh = h_first + pr, ww = side ? w_first + IW : w_first - 1;
+      const bool ok = hh >= 0 && hh < H && ww >= 0 && ww < W;
+      const int64_t off = (int64_t)min(max(hh, 0), H - 1) * W + min(max(ww, 0), W - 1);
+      uint32_t e[4];
+#pragma unroll
+      for (int ci = 0; ci < 4; ++ci) {
+        const bf16_t t = img[(int64_t)min(ci, CT - 1) * HW + off];
+        e[ci] = (ok && ci < CT) ? (uint32_t)t : 0u;
+      }
+      const uint32_t lo = e[0] | (e[1] << 16), hi = e[2] | (e[3] << 16);
+      if (side) *reinterpret_cast<uint4*>(tile + ((int64_t)pr * PW + IW + 2) * 4) = make_uint4(lo, hi, 0u, 0u);
+      else *reinterpret_cast<uint4*>(tile + (int64_t)pr * PW * 4) = make_uint4(0u, 0u, lo, hi);
+    }
+  } else {
+    for (int i = tid; i < rows * PW * 4; i += NT) {
+      const int ci = i & 3, cell = i >> 2;
+      const int pc = cell % PW, pr = cell / PW;
+      const int hh = h_first + pr, ww = w_first - 2 + pc;
+      const bool ok = ci < CT && pc >= 1 && pc <= IW + 2 && hh >= 0 && hh < H && ww >= 0 && ww < W;
+      const bf16_t t = img[(int64_t)min(ci, CT - 1) * HW + (int64_t)min(max(hh, 0), H - 1) * W + min(max(ww, 0), W - 1)];
+      tile[i] = ok ? t : (bf16_t)0;
+    }
+  }
+}
+
+// Weights of a thin-side conv as bf16 MFMA operand rows: wfrag[co][r][k], k = 4*s + ci
+// (zero where ci >= CT, s == 3 or co >= CW).
+//   Wk(co,ci,r,s) = W[co][ci][r][s]             (W canonical [CW][CT][3][3])
+//                 = W[ci][co][2-r][2-s]         (flip: W canonical [CT][CW][3][3], input gradient)
+__global__ void k_thin_pack_wfrag(const float* __restrict__ wcanon, bf16_t* __restrict__ wfrag, int CT, int CW,
+                                  int rows, int flip) {
+  const int i = blockIdx.x * NT + threadIdx.x;
+  if (i >= rows * 48) return;
+  const int k = i & 15, r = (i >> 4) % 3, co = i / 48;
+  const int s_ = k >> 2, ci = k & 3;
+  float v = 0.0f;
+  if (co < CW && ci < CT && s_ < 3)
+    v = flip ? wcanon[(((int64_t)ci * CW + co) * 3 + (2 - r)) * 3 + (2 - s_)]
+             : wcanon[(((int64_t)co * CT + ci) * 3 + r) * 3 + s_];
+  wfrag[i] = f32_to_bf16(v);
+}
+
+// Row L (0..255) of a workgroup's 256 x CW output tile -> pixel of the TH x TW patch.
+// Linear: row-major.  Grouped (GROUP2): rows 4G..4G+3 are the 2x2 pixel group G, so that the
+// four accumulator values a lane holds for one row quad are one group.
+template <bool GROUP2>
+__device__ __forceinline__ void thin_row_pixel(int L, int TW, int tw_shift, int& th, int& tw) {
+  if (GROUP2) {
+    const int G = L >> 2;
+    th = 2 * (G >> (tw_shift - 1)) + ((L >> 1) & 1);
+    tw = 2 * (G & ((TW >> 1) - 1)) + (L & 1);
+  } else {
+    th = L >> tw_shift;
+    tw = L & (TW - 1);
+  }
+}
+
+// Epilogue of the thin-in conv.  MODE 0: every check at run time (ragged patches, any activation);
+// MODE 1: interior patch, column statistics of the stored value, no activation;
+// MODE 2: interior, ReLU;  MODE 3: interior, no activation.
+// Element e of lane l in tile (i,j): row wave*64 + i*32 + (e/4)*8 + (l/32)*4 + e%4, channel j*32 + l%32.
+// Rows are staged through wave-private LDS so that global stores are 16 bytes wide.
+template <int NJ, int MODE, bool UPSUM>
+__device__ __forceinline__ void thin_epilogue(const t_floatx16 (&acc)[2][NJ], const float (&bs)[NJ],
+                                              bf16_t* __restrict__ stage, bf16_t* __restrict__ out_n, int H, int W,
+                                              int CW, int h0, int w0, int TW, int tw_shift, int act, bool want_stats,
+                                              float (&s1)[NJ], float (&s2)[NJ]) {
+  constexpr int SW = NJ * 32 + 8;                // staging row stride
+  constexpr int CPR = NJ * 4;                    // 16-byte chunks per pixel
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col_lane = lane & 31, row_lane = (lane >> 5) * 4;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    if (!UPSUM) {
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int lr = (e >> 2) * 8 + row_lane + (e & 3);
+          float v = acc[i][j][e] + bs[j];
+          if (MODE == 0) {
+            v = bf16_to_f32(f32_to_bf16(v));
+            if (want_stats) {
+              int th, tw;
+              thin_row_pixel<false>(wave * 64 + i * 32 + lr, TW, tw_shift, th, tw);
+              if (j * 32 + col_lane < CW && h0 + th < H && w0 + tw < W) { s1[j] += v; s2[j] = fmaf(v, v, s2[j]); }
+            }
+            v = apply_act(v, act);
+          } else if (MODE == 1) {
+            v = bf16_to_f32(f32_to_bf16(v));
+            s1[j] += v;
+            s2[j] = fmaf(v, v, s2[j]);
+          } else if (MODE == 2) {
+            v = fmaxf(v, 0.0f);                  // rounding is monotonic and keeps 0
+          }
+          stage[lr * SW + j * 32 + col_lane] = f32_to_bf16(v);
+        }
+      }
+#pragma unroll
+      for (int c = 0; c < (32 * CPR) / 64; ++c) {
+        const int idx = c * 64 + lane;
+        const int lr = idx / CPR, ch = idx % CPR;
+        int th, tw;
+        thin_row_pixel<false>(wave * 64 + i * 32 + lr, TW, tw_shift, th, tw);
+        const int hh = h0 + th, ww = w0 + tw;
+        if (MODE != 0 || (hh < H && ww < W && ch * 8 < CW))
+          *reinterpret_cast<uint4*>(out_n + ((int64_t)hh * W + ww) * CW + ch * 8) =
+              *reinterpret_cast<const uint4*>(&stage[lr * SW + ch * 8]);
+      }
+    } else {
+      // 2x2 sums: the row quad (e%4 = 0..3) of a lane is one pixel group
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) {
+#pragma unroll
+        for (int eg = 0; eg < 4; ++eg) {
+          const float v = ((acc[i][j][4 * eg] + bs[j]) + (acc[i][j][4 * eg + 1] + bs[j])) +
+                          ((acc[i][j][4 * eg + 2] + bs[j]) + (acc[i][j][4 * eg + 3] + bs[j]));
+          stage[(eg * 2 + (lane >> 5)) * SW + j * 32 + col_lane] = f32_to_bf16(v);
+        }
+      }
+      const int Hq = H >> 1, Wq = W >> 1;
+#pragma unroll
+      for (int c = 0; c < (8 * CPR + 63) / 64; ++c) {
+        const int idx = c * 64 + lane;
+        const int g8 = idx / CPR, ch = idx % CPR;
+        const int G = wave * 16 + i * 8 + g8;
+        const int hq = (h0 >> 1) + (G >> (tw_shift - 1)), wq = (w0 >> 1) + (G & ((TW >> 1) - 1));
+        if (idx < 8 * CPR && (MODE != 0 || (hq < Hq && wq < Wq && ch * 8 < CW)))
+          *reinterpret_cast<uint4*>(out_n + ((int64_t)hq * Wq + wq) * CW + ch * 8) =
+              *reinterpret_cast<const uint4*>(&stage[g8 * SW + ch * 8]);
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// thin-in conv.  A workgroup owns a TH x TW patch of one image (TH*TW = 256 pixels); each
+// wave computes 64 pixels x NJ*32 channels with three MFMA steps (one per filter row) per
+// 32x32 tile.  out: [n][H][W][CW], or with UPSUM [n][H/2][W/2][CW] holding 2x2 sums.
+// partial (optional): [patch][sum | sum of squares][CW] of the stored values.
+// ---------------------------------------------------------------------------
+template <int NJ, bool UPSUM>
+__global__ __launch_bounds__(NT) void k_thin_in_mfma(const bf16_t* __restrict__ thin, const bf16_t* __restrict__ wfrag,
+                                                     const float* __restrict__ bias, bf16_t* __restrict__ out,
+                                                     float* __restrict__ partial, int H, int W, int CT, int CW, int act,
+                                                     int TW, int tw_shift, int tiles_w, int tiles_h, int vec) {
+  constexpr int MAXT = 408;                     // (TH+2)*(TW+4) cells for every TW in {8,...,64}
+  constexpr int SW = NJ * 32 + 8;
+  __shared__ __attribute__((aligned(16))) bf16_t tile[MAXT * 4];
+  __shared__ __attribute__((aligned(16))) bf16_t stage_all[4 * 32 * SW];
+  __shared__ float sRed[4][2][NJ * 32];
+  const int TH = NT >> tw_shift;
+  const int PW = TW + 4;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int b = blockIdx.x;
+  const int tx = b % tiles_w; b /= tiles_w;
+  const int ty = b % tiles_h;
+  const int n = b / tiles_h;
+  const int h0 = ty * TH, w0 = tx * TW;
+  const int frag_row = lane & 31, g = lane >> 5;
+  const int col_lane = lane & 31;
+
+  t_bf16x8 bfrag[3][NJ];
+#pragma unroll
+  for (int r = 0; r < 3; ++r)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+      bfrag[r][j] = *reinterpret_cast<const t_bf16x8*>(&wfrag[((j * 32 + frag_row) * 3 + r) * 16 + g * 8]);
+  float bs[NJ];
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) bs[j] = (bias && j * 32 + col_lane < CW) ? bias[j * 32 + col_lane] : 0.0f;
+
+  thin_fill_patch(tile, thin + (int64_t)n * CT * H * W, H, W, CT, h0 - 1, w0, TH + 2, TW, vec != 0);
+  __syncthreads();
+
+  t_floatx16 acc[2][NJ];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    int th, tw;
+    thin_row_pixel<UPSUM>(wave * 64 + i * 32 + frag_row, TW, tw_shift, th, tw);
+#pragma unroll
+    for (int r = 0; r < 3; ++r) {
+      // k-chunk g: taps s = 2g, 2g+1 = cells tw + 1 + 2g, tw + 2 + 2g of patch row th + r
+      const bf16_t* src = &tile[((th + r) * PW + tw + 1 + 2 * g) * 4];
+      union { uint2 u[2]; t_bf16x8 v; } a;
+      a.u[0] = *reinterpret_cast<const uint2*>(src);
+      a.u[1] = *reinterpret_cast<const uint2*>(src + 4);
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, bfrag[r][j], acc[i][j], 0, 0, 0);
+    }
+  }
+
+  float s1[NJ], s2[NJ];
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) { s1[j] = 0.0f; s2[j] = 0.0f; }
+  bf16_t* stage = stage_all + wave * (32 * SW);
+  const bool interior = h0 + TH <= H && w0 + TW <= W && CW == NJ * 32;
+  if (UPSUM) {
+    bf16_t* out_n = out + (int64_t)n * (H >> 1) * (W >> 1) * CW;
+    if (interior) thin_epilogue<NJ, 3, true>(acc, bs, stage, out_n, H, W, CW, h0, w0, TW, tw_shift, act, false, s1, s2);
+    else thin_epilogue<NJ, 0, true>(acc, bs, stage, out_n, H, W, CW, h0, w0, TW, tw_shift, act, false, s1, s2);
+  } else {
+    bf16_t* out_n = out + (int64_t)n * H * W * CW;
+    const bool stats = partial != nullptr;
+    if (!interior || act == ACT_SIGMOID || (stats && act != ACT_NONE))
+      thin_epilogue<NJ, 0, false>(acc, bs, stage, out_n, H, W, CW, h0, w0, TW, tw_shift, act, stats, s1, s2);
+    else if (stats) thin_epilogue<NJ, 1, false>(acc, bs, stage, out_n, H, W, CW, h0, w0, TW, tw_shift, act, true, s1, s2);
+    else if (act == ACT_RELU) thin_epilogue<NJ, 2, false>(acc, bs, stage, out_n, H, W, CW, h0, w0, TW, tw_shift, act, false, s1, s2);
+    else thin_epilogue<NJ, 3, false>(acc, bs, stage, out_n, H, W, CW, h0, w0, TW, tw_shift, act, false, s1, s2);
+    if (stats) {
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) {
+        const float t1 = s1[j] + __shfl_xor(s1[j], 32, 64);
+        const float t2 = s2[j] + __shfl_xor(s2[j], 32, 64);
+        if (lane < 32) { sRed[wave][0][j * 32 + col_lane] = t1; sRed[wave][1][j * 32 + col_lane] = t2; }
+      }
+      __syncthreads();
+      for (int i = tid; i < 2 * NJ * 32; i += NT) {
+        const int q = i / (NJ * 32), c = i % (NJ * 32);
+        if (c < CW)
+          partial[((int64_t)blockIdx.x * 2 + q) * CW + c] = sRed[0][q][c] + sRed[1][q][c] + sRed[2][q][c] + sRed[3][q][c];
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// thin weight gradient:  D[cw][k] = sum over wide pixels q = (n,i,j) of wide[q][cw] * B[q][k],
+//   k = 16*r + 4*s + ct,   B[q][k] = sum_{a,b <= up} thin[n][ct][(i<<up) + r - 1 + a][(j<<up) + s - 1 + b].
+// first layer (up = 0): thin is the layer input, wide the output gradient: dW[cw][ct][r][s] = D[cw][k];
+// last layer: thin is the output gradient (at the resolution of the conv), wide the layer input
+// (at the stored resolution, which the conv reads through the x2 upsample if up = 1), and the
+// taps come out mirrored: dW[ct][cw][2-r][2-s] = D[cw][k].
+// The pixel is the reduction index of the MFMA; both operands are pixel-major in LDS (the wide
+// slab as loaded, the thin patch as described above, where B[q][16r .. 16r+11] is a contiguous
+// run and the next pixel starts 4 << up values later) and are read with the transposing LDS load:
+// within 16 lanes, lane 4*j+q supplies the address of 4 values of pixel j, lane i receives
+// value i of pixels 0..3.  A workgroup walks over patches of 256 wide pixels, each wave owning
+// 64 of them, and accumulates in registers; at the end the four waves are summed through LDS
+// in a fixed order and one partial [cw][64] is written.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ t_bf16x8 thin_tr_frag(const bf16_t* p0, const bf16_t* p1) {
+  t_short4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((t_lds_short4*)p0);
+  t_short4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((t_lds_short4*)p1);
+  union { short s[8]; t_bf16x8 v; } u;
+  u.s[0] = lo[0]; u.s[1] = lo[1]; u.s[2] = lo[2]; u.s[3] = lo[3];
+  u.s[4] = hi[0]; u.s[5] = hi[1]; u.s[6] = hi[2]; u.s[7] = hi[3];
+  return u.v;
+}
+
+template <int MI>   // CW = 32*MI wide channels
+__global__ __launch_bounds__(NT) void k_thin_wgrad_mfma(const bf16_t* __restrict__ thin, const bf16_t* __restrict__ wide,
+                                                        float* __restrict__ partial, int Hq, int Wq, int CT, int up,
+                                                        int TW, int tw_shift, int tiles_w, int tiles_h, int ntiles,
+                                                        int vec) {
+  constexpr int CW = 32 * MI;
+  constexpr int LA = CW + 16;
+  constexpr int MAXT = 1320;                    // ((TH<<up)+2) * ((TW<<up)+4) cells for every TW in {16,32,64}, up in {0,1}
+  __shared__ __attribute__((aligned(16))) bf16_t tile[MAXT * 4];
+  __shared__ __attribute__((aligned(16))) bf16_t sW[NT * LA];
+  const int TH = NT >> tw_shift;
+  const int IW = TW << up, PW = IW + 4, rows = (TH << up) + 2;
+  const int Ht = Hq << up, Wt = Wq << up;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int grp = lane >> 4, sl = lane & 15;
+
+  t_floatx16 acc[MI][2];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+  for (int t = blockIdx.x; t < ntiles; t += gridDim.x) {
+    int b = t;
+    const int tx = b % tiles_w; b /= tiles_w;
+    const int ty = b % tiles_h;
+    const int n = b / tiles_h;
+    const int h0 = ty * TH, w0 = tx * TW;
+    // wide slab first (its loads are the long ones): patch pixel p = th*TW + tw -> row p of sW
+    constexpr int CPP = CW / 8;                 // 16-byte chunks per pixel
+    uint4 wv[CPP];
+#pragma unroll
+    for (int c = 0; c < CPP; ++c) {
+      const int idx = c * NT + tid;
+      const int p = idx / CPP, ch = idx % CPP;
+      const int hh = h0 + (p >> tw_shift), ww = w0 + (p & (TW - 1));
+      const bool ok = hh < Hq && ww < Wq;
+      wv[c] = *reinterpret_cast<const uint4*>(wide + (((int64_t)n * Hq + min(hh, Hq - 1)) * Wq + min(ww, Wq - 1)) * CW + ch * 8);
+      if (!ok) { wv[c].x = 0u; wv[c].y = 0u; wv[c].z = 0u; wv[c].w = 0u; }
+    }
+    __syncthreads();                            // previous patch fully consumed
+    thin_fill_patch(tile, thin + (int64_t)n * CT * Ht * Wt, Ht, Wt, CT, (h0 << up) - 1, w0 << up, rows, IW, vec != 0);
+#pragma unroll
+    for (int c = 0; c < CPP; ++c) {
+      const int idx = c * NT + tid;
+      *reinterpret_cast<uint4*>(&sW[(idx / CPP) * LA + (idx % CPP) * 8]) = wv[c];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const int p0 = wave * 64 + ks * 16;       // 16 consecutive pixels of one patch row
+      const int th = p0 >> tw_shift, tw0 = p0 & (TW - 1);
+      const int psub = 8 * (grp >> 1) + (sl >> 2);
+      t_bf16x8 a[MI];
+#pragma unroll
+      for (int i = 0; i < MI; ++i) {
+        const bf16_t* q = &sW[(p0 + psub) * LA + i * 32 + 16 * (grp & 1) + 4 * (sl & 3)];
+        a[i] = thin_tr_frag(q, q + 4 * LA);
+      }
+      for (int ab = 0; ab < (1 << (2 * up)); ++ab) {
+        const int a_ = ab >> 1, b_ = ab & 1;
+        t_bf16x8 bfr[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const int r = min(2 * j + (grp & 1), 2);  // columns 48..63 are unused: any finite data
+          const bf16_t* q = &tile[(((th << up) + r + a_) * PW + 1 + ((tw0 + psub) << up) + (sl & 3) + b_) * 4];
+          bfr[j] = thin_tr_frag(q, q + (16 << up));
+        }
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bfr[j], acc[i][j], 0, 0, 0);
+      }
+    }
+  }
+  // sum the four waves in a fixed order through LDS (reusing the slab), then write [cw][64]
+  float* sF = reinterpret_cast<float*>(sW);     // MI*2*1024 floats <= NT*LA*2 bytes
+  for (int wv = 0; wv < 4; ++wv) {
+    __syncthreads();
+    if (wave == wv) {
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const int row = i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3), col = j * 32 + (lane & 31);
+            if (wv == 0) sF[row * 64 + col] = acc[i][j][e];
+            else sF[row * 64 + col] += acc[i][j][e];
+          }
+    }
+  }
+  __syncthreads();
+  for (int i = tid; i < CW * 64; i += NT) partial[(int64_t)blockIdx.x * CW * 64 + i] = sF[i];
+}
+
+// dW = sum over blocks of partial[b][cw][16*r + 4*s + ct]; 16 lanes per output, each summing
+// every 16th block, then a fixed-order shuffle tree.
+// mode 0: dW[cw][ct][r][s];  mode 1: dW[ct][cw][2-r][2-s]
+__global__ void k_thin_wgrad_mfma_reduce(const float* __restrict__ partial, int nblocks, int CW, int CT, int mode,
+                                         float* __restrict__ dw) {
+  const int total = CW * CT * 9;
+  const int gid = (blockIdx.x * NT + threadIdx.x) >> 4, sub = threadIdx.x & 15;
+  const int i = gid < total ? gid : total - 1;
+  const int tap = i % 9, ct = (i / 9) % CT, cw = i / (9 * CT);
+  const int r = tap / 3, s = tap % 3;
+  const float* src = partial + (int64_t)cw * 64 + 16 * r + 4 * s + ct;
+  float acc = 0.0f;
+#pragma unroll 4
+  for (int b = sub; b < nblocks; b += 16) acc += src[(int64_t)b * CW * 64];
+  acc += __shfl_xor(acc, 1, 64);
+  acc += __shfl_xor(acc, 2, 64);
+  acc += __shfl_xor(acc, 4, 64);
+  acc += __shfl_xor(acc, 8, 64);
+  if (gid < total && sub == 0) {
+    const int64_t o = mode == 0 ? (int64_t)i : (((int64_t)ct * CW + cw) * 3 + (2 - r)) * 3 + (2 - s);
+    dw[o] = acc;
+  }
+}
+
+struct ThinTile { int tw, shift, th, tiles_w, tiles_h, blocks; };
+ThinTile thin_tile(int n, int h, int w) {
+  ThinTile t;
+  t.tw = 8; t.shift = 3;
+  while (t.tw < 64 && t.tw < w) { t.tw <<= 1; ++t.shift; }
+  t.th = NT / t.tw;
+  t.tiles_w = (w + t.tw - 1) / t.tw;
+  t.tiles_h = (h + t.th - 1) / t.th;
+  t.blocks = n * t.tiles_h * t.tiles_w;
+  return t;
+}
+
+bool vec_ok(const void* p, int w) { return w % 8 == 0 && ((uintptr_t)p & 15) == 0; }
+
+}  // namespace
+
+bool thin_in_mfma_supported(int ct, int cw, int k, int up, int dtype) {
+  return dtype == AE_BF16 && k == 3 && !up && ct >= 1 && ct <= 4 && cw % 32 == 0 && cw <= 128;
+}
+
+int thin_in_mfma_blocks(int n, int h, int w) { return thin_tile(n, h, w).blocks; }
+
+int64_t thin_wfrag_bytes(int cw) { return (int64_t)((cw + 31) / 32) * 32 * 48 * 2; }
+
+// thin: planar [n][ct][h][w]; out: [n*h*w][cw], or with upsum (h, w even) [n*(h/2)*(w/2)][cw] holding the
+// sums over 2x2 pixel groups.  wfrag: scratch of thin_wfrag_bytes(cw) bytes.
+int launch_thin_in_mfma(const void* thin, const float* wcanon, void* wfrag, const float* bias, void* out, float* partial,
+                        int n, int h, int w, int ct, int cw, int flip, int act, int upsum, hipStream_t s) {
+  if (!thin_in_mfma_supported(ct, cw, 3, 0, AE_BF16)) return fail(AE_EINVAL, "thin_in_mfma: shape not supported");
+  if (upsum && ((h | w) & 1 || partial || act != ACT_NONE)) return fail(AE_EINVAL, "thin_in_mfma: bad 2x2-sum request");
+  const ThinTile t = thin_tile(n, h, w);
+  const int nj = cw / 32;
+  hipLaunchKernelGGL(k_thin_pack_wfrag, dim3((unsigned)((nj * 32 * 48 + NT - 1) / NT)), dim3(NT), 0, s, wcanon,
+                     (bf16_t*)wfrag, ct, cw, nj * 32, flip);
+  AE_TRY(launch_status("thin_pack_wfrag"));
+  const int vec = vec_ok(thin, w) ? 1 : 0;
+#define LAUNCH_TIM(NJV, UPV)                                                                                     \
+  hipLaunchKernelGGL((k_thin_in_mfma<NJV, UPV>), dim3((unsigned)t.blocks), dim3(NT), 0, s, (const bf16_t*)thin,  \
+                     (const bf16_t*)wfrag, bias, (bf16_t*)out, partial, h, w, ct, cw, act, t.tw, t.shift,        \
+                     t.tiles_w, t.tiles_h, vec)
+#define LAUNCH_TIM_NJ(UPV)              \
+  switch (nj) {                         \
+    case 1: LAUNCH_TIM(1, UPV); break;  \
+    case 2: LAUNCH_TIM(2, UPV); break;  \
+    case 3: LAUNCH_TIM(3, UPV); break;  \
+    default: LAUNCH_TIM(4, UPV); break; \
+  }
+  if (upsum) { LAUNCH_TIM_NJ(true) } else { LAUNCH_TIM_NJ(false) }
+#undef LAUNCH_TIM_NJ
+#undef LAUNCH_TIM
+  return launch_status("thin_in_mfma");
+}
+
+bool thin_wgrad_mfma_supported(int ct, int cw, int wq, int dtype) {
+  return dtype == AE_BF16 && ct >= 1 && ct <= 4 && cw % 32 == 0 && cw <= 128 && wq >= 16;
+}
+
+int thin_wgrad_mfma_blocks(int n, int hq, int wq) {
+  const int tiles = thin_tile(n, hq, wq).blocks;
+  return tiles < 768 ? tiles : 768;             // three persistent workgroups per compute unit
+}
+
+int64_t thin_wgrad_mfma_workspace_floats(int n, int hq, int wq, int cw) {
+  return (int64_t)thin_wgrad_mfma_blocks(n, hq, wq) * cw * 64;
+}
+
+// wide: [n*hq*wq][cw].  mode 0 (first layer): thin = planar layer input [n][ct][hq][wq], up = 0.
+// mode 1 (last layer): thin = planar output gradient [n][ct][hq<<up][wq<<up].
+int launch_thin_wgrad_mfma(const void* thin, const void* wide, float* workspace, float* dw_canonical, int n, int hq,
+                           int wq, int ct, int cw, int mode, int up, hipStream_t s) {
+  if (!thin_wgrad_mfma_supported(ct, cw, wq, AE_BF16) || up < 0 || up > 1 || (mode == 0 && up))
+    return fail(AE_EINVAL, "thin_wgrad_mfma: shape not supported");
+  const ThinTile t = thin_tile(n, hq, wq);
+  const int nblk = thin_wgrad_mfma_blocks(n, hq, wq);
+  const int vec = vec_ok(thin, wq << up) ? 1 : 0;
+#define LAUNCH_TWM(MIV)                                                                                         \
+  hipLaunchKernelGGL((k_thin_wgrad_mfma<MIV>), dim3((unsigned)nblk), dim3(NT), 0, s, (const bf16_t*)thin,        \
+                     (const bf16_t*)wide, workspace, hq, wq, ct, up, t.tw, t.shift, t.tiles_w, t.tiles_h, t.blocks, vec)
+  switch (cw / 32) {
+    case 1: LAUNCH_TWM(1); break;
+    case 2: LAUNCH_TWM(2); break;
+    case 3: LAUNCH_TWM(3); break;
+    default: LAUNCH_TWM(4); break;
+  }
+#undef LAUNCH_TWM
+  AE_TRY(launch_status("thin_wgrad_mfma"));
+  const int total = cw * ct * 9;
+  hipLaunchKernelGGL(k_thin_wgrad_mfma_reduce, dim3((unsigned)((total * 16 + NT - 1) / NT)), dim3(NT), 0, s, workspace,
+                     nblk, cw, ct, mode, dw_canonical);
+  return launch_status("thin_wgrad_mfma_reduce");
+}
+
+}  // namespace ae

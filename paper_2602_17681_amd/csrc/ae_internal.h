@@ -140,14 +140,16 @@ int launch_thin_in_conv(const void* thin, const float* wcanon, const float* bias
                         int h, int w, int ct, int cw, int flip, int act, int dtype, hipStream_t s);
 int launch_thin_out_conv(const void* wide, const float* wcanon, const float* bias, void* out, float* out_f32, int n,
                          int hc, int wc, int ct, int cw, int up, int act, int dtype, hipStream_t s);
+// bf16 matrix-core versions; see ae_conv_thin_mfma.hip
 bool thin_in_mfma_supported(int ct, int cw, int k, int up, int dtype);
 int thin_in_mfma_blocks(int n, int h, int w);   // = number of partial-sum blocks it writes
-int launch_thin_in_mfma(const void* thin, const float* wcanon, const float* bias, void* out, float* partial, int n,
-                        int h, int w, int ct, int cw, int flip, int act, hipStream_t s);
-bool thin_wgrad_mfma_supported(int ct, int cw, int w, int dtype);
-int64_t thin_wgrad_mfma_workspace_floats(int n, int h, int w, int cw);
-int launch_thin_wgrad_mfma(const void* thin, const void* wide, float* workspace, float* dw_canonical, int n, int h,
-                           int w, int ct, int cw, hipStream_t s);
+int64_t thin_wfrag_bytes(int cw);               // scratch for the repacked weights
+int launch_thin_in_mfma(const void* thin, const float* wcanon, void* wfrag, const float* bias, void* out, float* partial,
+                        int n, int h, int w, int ct, int cw, int flip, int act, int upsum, hipStream_t s);
+bool thin_wgrad_mfma_supported(int ct, int cw, int wq, int dtype);
+int64_t thin_wgrad_mfma_workspace_floats(int n, int hq, int wq, int cw);
+int launch_thin_wgrad_mfma(const void* thin, const void* wide, float* workspace, float* dw_canonical, int n, int hq,
+                           int wq, int ct, int cw, int mode, int up, hipStream_t s);
 int64_t thin_wgrad_workspace_floats(int64_t q_pixels, int ct, int cw);
 int launch_thin_wgrad(const void* thin, const void* wide, float* workspace, float* dw_canonical, int n, int hq, int wq,
                       int ct, int cw, int mode, int up, int dtype, hipStream_t s);

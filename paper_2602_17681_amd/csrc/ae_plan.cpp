@@ -255,8 +255,9 @@ int build_plan(const char* spec, int batch, int dtype, int bn_mode, Plan* plan) 
       else if (st.act == ACT_SIGMOID && dtype == AE_BF16) st.off_aux = take(raw_elems * 4);
       plan->max_full_elems = std::max(plan->max_full_elems, rows * st.cin);
       int64_t wel = (int64_t)st.cout * st.cin * st.k * st.k;
-      st.off_wpack = take(wel * es);
-      st.off_wpack_d = take(wel * es);
+      // thin layers keep their weights repacked as MFMA operand rows of the wide side
+      st.off_wpack = take(std::max(wel * es, st.thin == 1 ? thin_wfrag_bytes(st.cout) : (int64_t)0));
+      st.off_wpack_d = take(std::max(wel * es, st.thin == 2 ? thin_wfrag_bytes(st.cin) : (int64_t)0));
       if (st.has_bn) st.off_bn = take(6 * (int64_t)st.cout * 4);
       int64_t blocks = std::max<int64_t>((rows + 127) / 128, reduce_blocks(rows));  // finest partial-sum granularity
       if (st.thin == 1) blocks = std::max<int64_t>(blocks, thin_in_mfma_blocks(batch, st.hc, st.wc));
@@ -271,9 +272,13 @@ int build_plan(const char* spec, int batch, int dtype, int bn_mode, Plan* plan) 
           plan->max_wgrad_floats = std::max(plan->max_wgrad_floats,
                                             thin_wgrad_mfma_workspace_floats(batch, st.hc, st.wc, st.cout));
       }
-      else if (st.thin == 2)
+      else if (st.thin == 2) {
         plan->max_wgrad_floats = std::max(plan->max_wgrad_floats,
                                           thin_wgrad_workspace_floats(B * st.hin * st.win, st.cout, st.cin));
+        if (thin_wgrad_mfma_supported(st.cout, st.cin, st.win, dtype))
+          plan->max_wgrad_floats = std::max(plan->max_wgrad_floats,
+                                            thin_wgrad_mfma_workspace_floats(batch, st.hin, st.win, st.cin));
+      }
       else if (wgrad_mfma_supported(wa))
         plan->max_wgrad_floats = std::max(plan->max_wgrad_floats, wgrad_mfma_workspace_floats(st.cout, st.cin, st.k, rows));
       if (st.thin == 2) plan->max_partial_floats = std::max(plan->max_partial_floats, B * 2 * (int64_t)st.cout);
