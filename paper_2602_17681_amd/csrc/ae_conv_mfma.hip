@@ -102,9 +102,90 @@ __device__ __forceinline__ void igemm_store_interior(const floatx16 (&acc)[MI][N
   }
 }
 
+// ---- hand-scheduled LDS fragment reads of the DMA pipeline -------------------------------
+// The compiler orders an LDS read after EVERY outstanding global-to-LDS load (it cannot tell
+// the stages apart), which would serialise the pipeline; these reads are therefore issued as
+// inline assembly, and the waits on them (lgkmcnt) are placed by hand: LDS reads of a wave
+// return in order, so "at most n outstanding" identifies which fragments have arrived.  An
+// empty asm with the fragment as in/out operand keeps the MFMAs after the wait.
+typedef __attribute__((address_space(3))) char lds_char;
+// 16 bytes per lane from a buffer straight into LDS: lane l writes lds_wave_base + 16*l
+// (offsets past the buffer's range deliver zeros like any buffer load)
+__device__ __forceinline__ void dma_load16(__amdgpu_buffer_rsrc_t rsrc, char* lds_wave_base, unsigned voffset) {
+  typedef __attribute__((address_space(3))) void lds_void;
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)lds_wave_base, 16, voffset, 0, 0, 0);
+}
+template <int I, int N, int STRIDE>
+struct LdsReadFrags {
+  static __device__ __forceinline__ void run(uint4v (&f)[N], unsigned addr) {
+#if defined(__HIP_DEVICE_COMPILE__)             // the host pass only needs the kernel's stub
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(f[I]) : "v"(addr), "n"(I * STRIDE));
+#endif
+    LdsReadFrags<I + 1, N, STRIDE>::run(f, addr);
+  }
+};
+template <int N, int STRIDE>
+struct LdsReadFrags<N, N, STRIDE> {
+  static __device__ __forceinline__ void run(uint4v (&)[N], unsigned) {}
+};
+template <int I, int N>
+struct TieFrags {
+  static __device__ __forceinline__ void run(uint4v (&f)[N]) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm volatile("" : "+v"(f[I]));
+#endif
+    TieFrags<I + 1, N>::run(f);
+  }
+};
+template <int N>
+struct TieFrags<N, N> {
+  static __device__ __forceinline__ void run(uint4v (&)[N]) {}
+};
+// MFMAs of K-steps K .. KS-1 of one slab; fragments of step k arrived once at most
+// (KS-1-k)*(MI+NJ) reads are outstanding
+template <typename T, int KS, int K, int MI, int NJ>
+struct SlabSteps {
+  static __device__ __forceinline__ void run(uint4v (&a)[KS][MI], uint4v (&b)[KS][NJ], floatx16 (&acc)[MI][NJ]) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"((KS - 1 - K) * (MI + NJ)));
+#endif
+    TieFrags<0, MI>::run(a[K]);
+    TieFrags<0, NJ>::run(b[K]);
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) mma_step<T>(a[K][i], b[K][j], acc[i][j]);
+    __builtin_amdgcn_sched_barrier(0);           // keep these MFMAs ahead of the next step's wait
+    SlabSteps<T, KS, K + 1, MI, NJ>::run(a, b, acc);
+  }
+};
+template <typename T, int KS, int MI, int NJ>
+struct SlabSteps<T, KS, KS, MI, NJ> {
+  static __device__ __forceinline__ void run(uint4v (&)[KS][MI], uint4v (&)[KS][NJ], floatx16 (&)[MI][NJ]) {}
+};
+template <int K, int KS, int MI, int NJ, int BKB>
+struct SlabReads {
+  static __device__ __forceinline__ void run(uint4v (&a)[KS][MI], uint4v (&b)[KS][NJ], unsigned addr_a, unsigned addr_b,
+                                             const int (&lane_off)[KS]) {
+    LdsReadFrags<0, MI, 32 * BKB>::run(a[K], addr_a + (unsigned)lane_off[K]);
+    LdsReadFrags<0, NJ, 32 * BKB>::run(b[K], addr_b + (unsigned)lane_off[K]);
+    SlabReads<K + 1, KS, MI, NJ, BKB>::run(a, b, addr_a, addr_b, lane_off);
+  }
+};
+template <int KS, int MI, int NJ, int BKB>
+struct SlabReads<KS, KS, MI, NJ, BKB> {
+  static __device__ __forceinline__ void run(uint4v (&)[KS][MI], uint4v (&)[KS][NJ], unsigned, unsigned, const int (&)[KS]) {}
+};
+
 // INTERIOR: the host guarantees M % BM == 0, N % BN == 0, 16-byte aligned rows, no sigmoid, no
 // auxiliary copy and no activation together with statistics, so the epilogue needs no checks.
-template <typename T, int BM, int BN, int WGM, int WGN, int BKB, bool INTERIOR>
+// DMA: the slabs go from global memory straight into LDS (buffer loads with the LDS
+// destination: lane l of a wave writes 16 bytes at base + 16*l, which is exactly the loader's
+// linear slot order), three stages deep, so loads run two slabs ahead without holding
+// registers.  A wave waits for its own loads of the slab it is about to read (vmcnt), then
+// the workgroup barrier makes every wave's loads visible and also guarantees that the stage
+// about to be refilled has been read by everybody.
+template <typename T, int BM, int BN, int WGM, int WGN, int BKB, bool INTERIOR, bool DMA>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k_igemm(IgemmParams p) {
   static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
   static_assert(BKB == 64 || BKB == 128, "slab row bytes");
@@ -116,11 +197,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   constexpr int MI = WM / 32, NJ = WN / 32;     // 32x32 MFMA tiles per wave
   constexpr int A_CHUNKS = BM / RSTEP, B_CHUNKS = BN / RSTEP;
   constexpr int SW = WN + 16 / ES;              // staging row stride of the epilogue (elements): +16 bytes
-  constexpr int SLAB_BYTES = 2 * (BM + BN) * BKB;
+  constexpr int NSTAGE = DMA ? 3 : 2;
+  constexpr int SLAB_BYTES = NSTAGE * (BM + BN) * BKB;
   constexpr int STAGE_BYTES = 4 * 32 * SW * ES;
   __shared__ __attribute__((aligned(16))) char smem[SLAB_BYTES > STAGE_BYTES ? SLAB_BYTES : STAGE_BYTES];
-  char* const sA = smem;                        // [2][BM*BKB]
-  char* const sB = smem + 2 * BM * BKB;         // [2][BN*BKB]
+  char* const sA = smem;                        // [NSTAGE][BM*BKB]
+  char* const sB = smem + NSTAGE * BM * BKB;    // [NSTAGE][BN*BKB]
   __shared__ float sRed[WGM][2][BN];            // [wave row][sum | sumsq][column]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -219,6 +301,44 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
   const int KT = p.K / BK;
+  if constexpr (DMA) {
+    constexpr int L = A_CHUNKS + B_CHUNKS;       // loads per thread and slab
+    static_assert(RSTEP * BKB == 4096, "one pass of the loader covers 4 KB");
+#define IGEMM_DMA(STG)                                                                                       \
+  {                                                                                                          \
+    if (ci0 == 0) IGEMM_TAP();                                                                               \
+    char* const da = sA + (STG) * BM * BKB + wave * 1024;                                                    \
+    char* const db = sB + (STG) * BN * BKB + wave * 1024;                                                    \
+    _Pragma("unroll") for (int i = 0; i < A_CHUNKS; ++i)                                                     \
+        dma_load16(rX, da + i * 4096, a_off[i] + (unsigned)ci0 * (unsigned)ES);                              \
+    _Pragma("unroll") for (int i = 0; i < B_CHUNKS; ++i)                                                     \
+        dma_load16(rW, db + i * 4096, b_off[i] + kbyte);                                                     \
+    ci0 += BK;                                                                                               \
+    kbyte += BKB;                                                                                            \
+    if (ci0 == p.Cin) { ci0 = 0; ++rs; }                                                                     \
+  }
+    constexpr int KS = BKB / 32;
+    const unsigned lds_a = (unsigned)(size_t)(lds_char*)sA + (unsigned)(wm * WM * BKB);
+    const unsigned lds_b = (unsigned)(size_t)(lds_char*)sB + (unsigned)(wn * WN * BKB);
+    IGEMM_DMA(0);
+    if (KT > 1) IGEMM_DMA(1);
+    int cur = 0, nxt = 2;
+    for (int kt = 0; kt < KT; ++kt) {
+      // vmcnt(n): at most n of this wave's loads outstanding (they complete in order);
+      // the other counters are left alone (expcnt 7, lgkmcnt 15)
+      if (kt + 1 < KT) __builtin_amdgcn_s_waitcnt((L & 15) | ((L >> 4) << 14) | 0x0F70);
+      else __builtin_amdgcn_s_waitcnt(0x0F70);
+      __builtin_amdgcn_s_barrier();
+      uint4v fa[KS][MI], fb[KS][NJ];
+      SlabReads<0, KS, MI, NJ, BKB>::run(fa, fb, lds_a + (unsigned)(cur * BM * BKB), lds_b + (unsigned)(cur * BN * BKB), lane_off);
+      if (kt + 2 < KT) IGEMM_DMA(nxt);
+      SlabSteps<T, KS, 0, MI, NJ>::run(fa, fb, acc);
+      cur = cur == 2 ? 0 : cur + 1;
+      nxt = nxt == 2 ? 0 : nxt + 1;
+    }
+#undef IGEMM_DMA
+    __syncthreads();                             // every wave is done with the slabs: the epilogue reuses the memory
+  } else {
   uint4v ra0[A_CHUNKS], rb0[B_CHUNKS], ra1[A_CHUNKS], rb1[B_CHUNKS];
   IGEMM_LOAD(ra0, rb0);
   if (KT > 1) IGEMM_LOAD(ra1, rb1);
@@ -236,6 +356,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
     IGEMM_COMPUTE(1);
     if (kt + 2 < KT) IGEMM_STORE(0, ra0, rb0);
     __syncthreads();
+  }
   }
 #undef IGEMM_TAP
 #undef IGEMM_LOAD
@@ -331,8 +452,8 @@ IgemmTile pick_tile(int64_t M, int cout, int cin, int es) {
   const int64_t tiles_n = (cout + bn - 1) / bn;
   int bm = es == 2 ? 256 : 128;                 // 256-row tiles: bf16 only (register budget)
   if (((M + 255) / 256) * tiles_n < 512) bm = 128;
-  int bkb = (cin * es) % 128 == 0 ? 128 : 64;
-  if (bm == 256) bkb = 64;                      // 256-row tiles with 128-byte slabs exceed the budget of two waves per SIMD
+  (void)cin;
+  const int bkb = 64;                           // three LDS stages of 64-byte slabs: 2-3 workgroups per compute unit
   return IgemmTile{bm, bn, bkb};
 }
 
@@ -371,8 +492,8 @@ int launch_conv_mfma(const ConvArgs& a, hipStream_t s) {
                         !(a.partial && a.act != ACT_NONE);
 #define IGEMM_LAUNCH_K(T, BMV, BNV, GM, GN, KB)                                                        \
   do {                                                                                                 \
-    if (interior) hipLaunchKernelGGL((k_igemm<T, BMV, BNV, GM, GN, KB, true>), grid, dim3(256), 0, s, p); \
-    else hipLaunchKernelGGL((k_igemm<T, BMV, BNV, GM, GN, KB, false>), grid, dim3(256), 0, s, p);      \
+    if (interior) hipLaunchKernelGGL((k_igemm<T, BMV, BNV, GM, GN, KB, true, true>), grid, dim3(256), 0, s, p); \
+    else hipLaunchKernelGGL((k_igemm<T, BMV, BNV, GM, GN, KB, false, true>), grid, dim3(256), 0, s, p); \
   } while (0)
 #define IGEMM_LAUNCH_T(T, BMV, BNV, GM, GN)                                                            \
   do {                                                                                                 \
@@ -616,24 +737,166 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
     }
 }
 
-// dW[co][ci][r][s] = sum over splits of partial[split][co][(r,s,ci)], in split order
-__global__ void k_wgrad_reduce(const float* __restrict__ partial, int splits, int Cout, int Cin, int taps,
-                               float* __restrict__ dw) {
+// The same kernel for images whose width is a multiple of the slab depth BK: a slab is then BK
+// consecutive pixels of ONE image row, so the sample, the row and the row's validity for the
+// block's tap are uniform (scalar registers, advanced incrementally) and a thread's share of the
+// address arithmetic is one add, one compare and one select per 16-byte load.  The output
+// gradient advances through the scalar offset of the buffer load.  Every slab is full (the
+// host makes the splits multiples of BK).
+template <typename T, int BM, int BN, int BK>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k_wgrad_rows(WgradParams p) {
+  constexpr int ES = (int)sizeof(T);
+  constexpr int EPC = 16 / ES;
+  constexpr int LPAD = 32;
+  constexpr int LA = BM + LPAD, LB = BN + LPAD;
+  constexpr int WM = BM / 2, WN = BN / 2;
+  constexpr int MI = WM / 32, NJ = WN / 32;
+  constexpr int A_TPR = BM / EPC, B_TPR = BN / EPC;
+  constexpr int A_CHUNKS = BK * A_TPR / 256, B_CHUNKS = BK * B_TPR / 256;
+  static_assert(A_CHUNKS >= 1 && B_CHUNKS >= 1, "slab too small for 256 loader threads");
+  __shared__ __attribute__((aligned(16))) T sA[2][BK * LA];
+  __shared__ __attribute__((aligned(16))) T sB[2][BK * LB];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int taps = p.ksz * p.ksz;
+  int b = blockIdx.x;
+  const int tap = b % taps; b /= taps;
+  const int tn = b % p.tiles_n; b /= p.tiles_n;
+  const int tm = b % p.tiles_m;
+  const int split = b / p.tiles_m;
+  const int r = tap / p.ksz, s = tap - r * p.ksz;
+  const int pad = (p.ksz - 1) >> 1;
+  const int co0 = tm * BM, ci0 = tn * BN;
+  const int Hin = p.Hc >> p.up, Win = p.Wc >> p.up;
+  const int64_t m_begin = (int64_t)split * p.rows_per_split;
+  const int64_t m_end = (m_begin + p.rows_per_split < p.M) ? m_begin + p.rows_per_split : p.M;
+  const int KT = (int)((m_end - m_begin) / BK);
+
+  const __amdgpu_buffer_rsrc_t rX = make_rsrc(p.x, p.x_bytes);
+  const __amdgpu_buffer_rsrc_t rDY = make_rsrc(p.dy, p.dy_bytes);
+  unsigned a_voff[A_CHUNKS], b_voff[B_CHUNKS];
+  int b_pw[B_CHUNKS];
+#pragma unroll
+  for (int i = 0; i < A_CHUNKS; ++i) {
+    const int id = tid + i * 256;
+    a_voff[i] = (unsigned)(id / A_TPR) * (unsigned)(p.Cout * ES) + (unsigned)(co0 * ES) + (unsigned)(id % A_TPR) * 16u;
+  }
+#pragma unroll
+  for (int i = 0; i < B_CHUNKS; ++i) {
+    const int id = tid + i * 256;
+    b_pw[i] = id / B_TPR + s - pad;
+    b_voff[i] = (unsigned)(ci0 * ES) + (unsigned)(id % B_TPR) * 16u;
+  }
+  // coordinates of the next slab to load (uniform)
+  unsigned a_soff = (unsigned)m_begin * (unsigned)(p.Cout * ES);
+  int w0 = (int)((unsigned)m_begin % (unsigned)p.Wc);
+  int h = (int)(((unsigned)m_begin / (unsigned)p.Wc) % (unsigned)p.Hc);
+  int n = (int)((unsigned)m_begin / ((unsigned)p.Wc * (unsigned)p.Hc));
+  const unsigned cin_bytes = (unsigned)(p.Cin * ES);
+#define WGRAD_LOAD(RA, RB)                                                                                   \
+  {                                                                                                          \
+    _Pragma("unroll") for (int i = 0; i < A_CHUNKS; ++i)                                                     \
+        RA[i] = __builtin_amdgcn_raw_buffer_load_b128(rDY, a_voff[i], a_soff, 0);                            \
+    const int hh = h + r - pad;                                                                              \
+    const bool row_ok = hh >= 0 && hh < p.Hc;                                                                \
+    const unsigned row_base = ((unsigned)n * (unsigned)Hin + (unsigned)((row_ok ? hh : 0) >> p.up)) * (unsigned)Win * cin_bytes; \
+    _Pragma("unroll") for (int i = 0; i < B_CHUNKS; ++i) {                                                   \
+      const int ww = w0 + b_pw[i];                                                                           \
+      const bool ok = row_ok && (unsigned)ww < (unsigned)p.Wc;                                               \
+      const unsigned off = ok ? row_base + (unsigned)(ww >> p.up) * cin_bytes + b_voff[i] : kOob;            \
+      RB[i] = __builtin_amdgcn_raw_buffer_load_b128(rX, off, 0, 0);                                          \
+    }                                                                                                        \
+    a_soff += (unsigned)(BK * p.Cout * ES);                                                                  \
+    w0 += BK;                                                                                                \
+    if (w0 == p.Wc) { w0 = 0; if (++h == p.Hc) { h = 0; ++n; } }                                             \
+  }
+#define WGRAD_STORE(BUF, RA, RB)                                                                             \
+  {                                                                                                          \
+    _Pragma("unroll") for (int i = 0; i < A_CHUNKS; ++i) {                                                   \
+      const int id = tid + i * 256;                                                                          \
+      *reinterpret_cast<uint4v*>(&sA[BUF][(id / A_TPR) * LA + (id % A_TPR) * EPC]) = RA[i];                  \
+    }                                                                                                        \
+    _Pragma("unroll") for (int i = 0; i < B_CHUNKS; ++i) {                                                   \
+      const int id = tid + i * 256;                                                                          \
+      *reinterpret_cast<uint4v*>(&sB[BUF][(id / B_TPR) * LB + (id % B_TPR) * EPC]) = RB[i];                  \
+    }                                                                                                        \
+  }
+#define WGRAD_COMPUTE(BUF) wgrad_compute<T, MI, NJ, BK, LA, LB>(&sA[BUF][wm * WM], &sB[BUF][wn * WN], lane, acc)
+
+  floatx16 acc[MI][NJ];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+  uint4v ra0[A_CHUNKS], rb0[B_CHUNKS], ra1[A_CHUNKS], rb1[B_CHUNKS];
+  WGRAD_LOAD(ra0, rb0);
+  if (KT > 1) WGRAD_LOAD(ra1, rb1);
+  WGRAD_STORE(0, ra0, rb0);
+  __syncthreads();
+  for (int kt = 0; kt < KT; kt += 2) {
+    if (kt + 2 < KT) WGRAD_LOAD(ra0, rb0);
+    WGRAD_COMPUTE(0);
+    if (kt + 1 < KT) WGRAD_STORE(1, ra1, rb1);
+    __syncthreads();
+    if (kt + 1 >= KT) break;
+    if (kt + 3 < KT) WGRAD_LOAD(ra1, rb1);
+    WGRAD_COMPUTE(1);
+    if (kt + 2 < KT) WGRAD_STORE(0, ra0, rb0);
+    __syncthreads();
+  }
+#undef WGRAD_LOAD
+#undef WGRAD_STORE
+#undef WGRAD_COMPUTE
+
+  float* __restrict__ P = p.partial + (int64_t)split * p.Cout * p.K;
+  const int col_lane = lane & 31, row_lane = (lane >> 5) * 4;
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      const int ci = ci0 + wn * WN + j * 32 + col_lane;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int co = co0 + wm * WM + i * 32 + (e >> 2) * 8 + row_lane + (e & 3);
+        P[(int64_t)co * p.K + tap * p.Cin + ci] = acc[i][j][e];   // tiles divide C_out and C_in exactly
+      }
+    }
+}
+
+// dW[co][ci][r][s] = sum over splits of partial[split][co][(r,s,ci)].  A workgroup owns 64
+// consecutive outputs; wave v sums splits v, v+4, ... (independent loads, several in flight),
+// then the four waves are combined in a fixed order.
+__global__ __launch_bounds__(256) void k_wgrad_reduce(const float* __restrict__ partial, int splits, int Cout, int Cin,
+                                                      int taps, float* __restrict__ dw) {
+  __shared__ float sm[4][64];
   const int64_t total = (int64_t)Cout * taps * Cin;
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
-    float acc = 0.0f;
-    for (int sp = 0; sp < splits; ++sp) acc += partial[(int64_t)sp * total + i];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t i = (int64_t)blockIdx.x * 64 + lane;
+  float acc = 0.0f;
+  if (i < total) {
+    const float* src = partial + i;
+#pragma unroll 8
+    for (int sp = wave; sp < splits; sp += 4) acc += src[(int64_t)sp * total];
+  }
+  sm[wave][lane] = acc;
+  __syncthreads();
+  if (wave == 0 && i < total) {
+    const float t = (sm[0][lane] + sm[1][lane]) + (sm[2][lane] + sm[3][lane]);
     const int ci = (int)(i % Cin);
-    const int64_t t = i / Cin;
-    const int tap = (int)(t % taps);
-    const int co = (int)(t / taps);
-    dw[((int64_t)co * Cin + ci) * taps + tap] = acc;
+    const int64_t q = i / Cin;
+    const int tap = (int)(q % taps);
+    const int co = (int)(q / taps);
+    dw[((int64_t)co * Cin + ci) * taps + tap] = t;
   }
 }
 
-struct WgradPlan { int bm, bn, tiles_m, tiles_n, splits, rows_per_split; };
+struct WgradPlan { int bm, bn, bk, tiles_m, tiles_n, splits, rows_per_split; };   // bk = 0: generic kernel
 
-WgradPlan plan_wgrad(int cout, int cin, int k, int64_t rows) {
+WgradPlan plan_wgrad(int cout, int cin, int k, int64_t rows, int wc, int es) {
   WgradPlan w;
   w.bm = cout % 128 == 0 ? 128 : 64;
   w.bn = cin % 128 == 0 ? 128 : 64;
@@ -645,8 +908,12 @@ WgradPlan plan_wgrad(int cout, int cin, int k, int64_t rows) {
   const int64_t max_splits = (rows + 511) / 512;        // at least 512 pixels per split
   if (splits > max_splits) splits = max_splits;
   if (splits < 1) splits = 1;
+  // row-slab kernel: slabs of bk pixels that never straddle an image row
+  const int bk_big = es == 2 ? 64 : 32;
+  w.bk = wc % bk_big == 0 ? bk_big : (wc % (bk_big / 2) == 0 ? bk_big / 2 : 0);
+  const int gran = w.bk ? w.bk : 32;
   int64_t rps = (rows + splits - 1) / splits;
-  rps = (rps + 31) / 32 * 32;
+  rps = (rps + gran - 1) / gran * gran;
   w.rows_per_split = (int)rps;
   w.splits = (int)((rows + rps - 1) / rps);
   return w;
@@ -664,14 +931,14 @@ bool wgrad_mfma_supported(const WgradArgs& a) {
 }
 
 int64_t wgrad_mfma_workspace_floats(int cout, int cin, int k, int64_t rows) {
-  const WgradPlan w = plan_wgrad(cout, cin, k, rows);
+  const WgradPlan w = plan_wgrad(cout, cin, k, rows, 0, 2);
   return (int64_t)w.splits * cout * cin * k * k;
 }
 
 int launch_wgrad_mfma(const WgradArgs& a, float* workspace, hipStream_t s) {
   if (!wgrad_mfma_supported(a)) return fail(AE_EINVAL, "wgrad_mfma: shape not supported");
   const int64_t rows = (int64_t)a.n * a.hc * a.wc;
-  const WgradPlan w = plan_wgrad(a.cout, a.cin, a.k, rows);
+  const WgradPlan w = plan_wgrad(a.cout, a.cin, a.k, rows, a.wc, (int)dtype_size(a.dtype));
   WgradParams p;
   p.x = a.x; p.dy = a.dy; p.partial = workspace;
   p.M = rows; p.Cout = a.cout; p.Cin = a.cin; p.Hc = a.hc; p.Wc = a.wc; p.ksz = a.k; p.up = a.up;
@@ -701,14 +968,23 @@ int launch_wgrad_mfma(const WgradArgs& a, float* workspace, hipStream_t s) {
     if (pow2) WGRAD_LAUNCH_P(T, true);       \
     else WGRAD_LAUNCH_P(T, false);           \
   } while (0)
-  if (a.dtype == AE_BF16) WGRAD_LAUNCH(bf16_t);
+#define WGRAD_ROWS(T, BKV)                                                                              \
+  do {                                                                                                  \
+    if (w.bm == 128 && w.bn == 128) hipLaunchKernelGGL((k_wgrad_rows<T, 128, 128, BKV>), grid, dim3(256), 0, s, p); \
+    else if (w.bm == 128) hipLaunchKernelGGL((k_wgrad_rows<T, 128, 64, BKV>), grid, dim3(256), 0, s, p); \
+    else if (w.bn == 128) hipLaunchKernelGGL((k_wgrad_rows<T, 64, 128, BKV>), grid, dim3(256), 0, s, p); \
+    else hipLaunchKernelGGL((k_wgrad_rows<T, 64, 64, BKV>), grid, dim3(256), 0, s, p);                  \
+  } while (0)
+  if (w.bk && a.dtype == AE_BF16) { if (w.bk == 64) WGRAD_ROWS(bf16_t, 64); else WGRAD_ROWS(bf16_t, 32); }
+  else if (w.bk) { if (w.bk == 32) WGRAD_ROWS(float, 32); else WGRAD_ROWS(float, 16); }
+  else if (a.dtype == AE_BF16) WGRAD_LAUNCH(bf16_t);
   else WGRAD_LAUNCH(float);
+#undef WGRAD_ROWS
 #undef WGRAD_LAUNCH_P
 #undef WGRAD_LAUNCH
   AE_TRY(launch_status("wgrad_mfma"));
   const int64_t total = (int64_t)a.cout * a.cin * a.k * a.k;
-  int64_t g = (total + 255) / 256;
-  if (g > 4096) g = 4096;
+  const int64_t g = (total + 63) / 64;
   hipLaunchKernelGGL(k_wgrad_reduce, dim3((unsigned)g), dim3(256), 0, s, workspace, w.splits, a.cout, a.cin, a.k * a.k,
                      a.dw_canonical);
   return launch_status("wgrad_reduce");
