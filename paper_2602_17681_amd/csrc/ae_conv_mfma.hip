@@ -57,6 +57,15 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsig
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
 }
 
+// Workgroups are handed to the 8 accelerator dies (XCDs, each with its own L2) round-robin by
+// workgroup id.  This maps the hardware id to a logical one such that each XCD works on one
+// contiguous range of logical ids, so that workgroups which share operand rows (neighbouring
+// tiles, the taps of one tile) hit in the same L2.
+__device__ __forceinline__ int xcd_logical_block(int b, int nb) {
+  const int per = nb >> 3;                       // full rounds of 8
+  return b < (per << 3) ? (b & 7) * per + (b >> 3) : b;
+}
+
 template <typename T> __device__ __forceinline__ void mma_step(const uint4v& a, const uint4v& b, floatx16& c);
 template <> __device__ __forceinline__ void mma_step<bf16_t>(const uint4v& a, const uint4v& b, floatx16& c) {
   c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
@@ -207,8 +216,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
-  const int tile_n = blockIdx.x % p.tiles_n;
-  const int64_t tile_m = blockIdx.x / p.tiles_n;
+  const int lb = xcd_logical_block((int)blockIdx.x, (int)gridDim.x);
+  const int tile_n = lb % p.tiles_n;
+  const int64_t tile_m = lb / p.tiles_n;
   const int64_t m0 = tile_m * BM;
   const int n0 = tile_n * BN;
   const int pad = (p.ksz - 1) >> 1;
@@ -630,7 +640,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   // block -> (split, tile_m, tile_n, tap): the tap varies fastest so that the blocks
   // sharing a dY slab and overlapping x slabs run at the same time
   const int taps = p.ksz * p.ksz;
-  int b = blockIdx.x;
+  int b = xcd_logical_block((int)blockIdx.x, (int)gridDim.x);
   const int tap = b % taps; b /= taps;
   const int tn = b % p.tiles_n; b /= p.tiles_n;
   const int tm = b % p.tiles_m;
@@ -760,7 +770,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int taps = p.ksz * p.ksz;
-  int b = blockIdx.x;
+  int b = xcd_logical_block((int)blockIdx.x, (int)gridDim.x);
   const int tap = b % taps; b /= taps;
   const int tn = b % p.tiles_n; b /= p.tiles_n;
   const int tm = b % p.tiles_m;
