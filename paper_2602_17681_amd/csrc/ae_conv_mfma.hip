@@ -111,6 +111,96 @@ __device__ __forceinline__ void igemm_store_interior(const floatx16 (&acc)[MI][N
   }
 }
 
+// Epilogue shared by the implicit-GEMM kernels.  Accumulator element e of lane l in tile (i,j):
+//     row = wm*WM + i*32 + (e/4)*8 + (l/32)*4 + e%4,  column = wn*WN + j*32 + l%32
+// Results go through a wave-private LDS staging area (the operand buffers are free: the K loop
+// ended on a barrier) so that global stores are 16 bytes wide and each instruction covers
+// whole row segments.  smem: at least 4*32*(WN + 16/sizeof(T))*sizeof(T) bytes; sRed: [WGM][2][BN].
+template <typename T, int BM, int BN, int WGM, int WGN, bool INTERIOR>
+__device__ __forceinline__ void igemm_epilogue(floatx16 (&acc)[BM / WGM / 32][BN / WGN / 32], const IgemmParams& p,
+                                               char* smem, float (*sRed)[2][BN], int64_t m0, int n0, int64_t tile_m) {
+  constexpr int ES = (int)sizeof(T);
+  constexpr int WM = BM / WGM, WN = BN / WGN;
+  constexpr int MI = WM / 32, NJ = WN / 32;
+  constexpr int SW = WN + 16 / ES;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+  T* __restrict__ Y = (T*)p.y;
+  const int col_lane = lane & 31, row_lane = (lane >> 5) * 4;
+  const bool wide_store = ((p.N * ES) % 16 == 0) && !p.y_aux;
+  T* stage = reinterpret_cast<T*>(smem) + wave * (32 * SW);
+  float s1[NJ], s2[NJ];
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) { s1[j] = 0.0f; s2[j] = 0.0f; }
+  if constexpr (INTERIOR) {
+    float bias[NJ];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) bias[j] = p.bias ? p.bias[n0 + wn * WN + j * 32 + col_lane] : 0.0f;
+    T* yrow = Y + (m0 + wm * WM) * p.N + n0 + wn * WN;
+    if (p.partial) igemm_store_interior<T, MI, NJ, WN, SW, true, false>(acc, bias, stage, yrow, p.N, lane, s1, s2);
+    else if (p.act == ACT_RELU) igemm_store_interior<T, MI, NJ, WN, SW, false, true>(acc, bias, stage, yrow, p.N, lane, s1, s2);
+    else igemm_store_interior<T, MI, NJ, WN, SW, false, false>(acc, bias, stage, yrow, p.N, lane, s1, s2);
+  } else {
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) {
+        const int col = n0 + wn * WN + j * 32 + col_lane;
+        const bool col_ok = col < p.N;
+        const float bias = (p.bias && col_ok) ? p.bias[col] : 0.0f;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int lr = (e >> 2) * 8 + row_lane + (e & 3);
+          const int64_t m = m0 + wm * WM + i * 32 + lr;
+          const float v = round_to_storage<T>(acc[i][j][e] + bias);   // the stored conv result
+          if (p.partial && m < p.M && col_ok) { s1[j] += v; s2[j] = fmaf(v, v, s2[j]); }
+          const float a = apply_act(v, p.act);
+          if (wide_store) {
+            Store<T>::st(&stage[lr * SW + j * 32 + col_lane], a);
+          } else if (m < p.M && col_ok) {
+            Store<T>::st(&Y[m * p.N + col], a);
+            if (p.y_aux) p.y_aux[m * p.N + col] = a;
+          }
+        }
+      }
+      if (wide_store) {
+        constexpr int EPC = 16 / ES;               // elements per 16-byte chunk
+        constexpr int CPRO = WN / EPC;             // chunks per staged row
+#pragma unroll
+        for (int c = 0; c < (32 * CPRO) / 64; ++c) {
+          const int idx = c * 64 + lane;
+          const int lr = idx / CPRO, ch = idx % CPRO;
+          const int64_t m = m0 + wm * WM + i * 32 + lr;
+          const int col0 = n0 + wn * WN + ch * EPC;
+          if (m < p.M && col0 < p.N)
+            *reinterpret_cast<uint4v*>(Y + m * p.N + col0) = *reinterpret_cast<const uint4v*>(&stage[lr * SW + ch * EPC]);
+        }
+      }
+    }
+  }
+  if (p.partial) {
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      float t1 = s1[j] + __shfl_xor(s1[j], 32, 64);
+      float t2 = s2[j] + __shfl_xor(s2[j], 32, 64);
+      if (lane < 32) {
+        sRed[wm][0][wn * WN + j * 32 + col_lane] = t1;
+        sRed[wm][1][wn * WN + j * 32 + col_lane] = t2;
+      }
+    }
+  }
+  if (p.partial) {
+    __syncthreads();
+    for (int i = tid; i < 2 * BN; i += 256) {
+      const int q = i / BN, c = i - q * BN;
+      float t = 0.0f;
+#pragma unroll
+      for (int g = 0; g < WGM; ++g) t += sRed[g][q][c];
+      if (n0 + c < p.N) p.partial[(tile_m * 2 + q) * p.N + n0 + c] = t;
+    }
+  }
+}
+
 // ---- hand-scheduled LDS fragment reads of the DMA pipeline -------------------------------
 // The compiler orders an LDS read after EVERY outstanding global-to-LDS load (it cannot tell
 // the stages apart), which would serialise the pipeline; these reads are therefore issued as
@@ -176,8 +266,8 @@ template <int K, int KS, int MI, int NJ, int BKB>
 struct SlabReads {
   static __device__ __forceinline__ void run(uint4v (&a)[KS][MI], uint4v (&b)[KS][NJ], unsigned addr_a, unsigned addr_b,
                                              const int (&lane_off)[KS]) {
-    LdsReadFrags<0, MI, 32 * BKB>::run(a[K], addr_a + (unsigned)lane_off[K]);
     LdsReadFrags<0, NJ, 32 * BKB>::run(b[K], addr_b + (unsigned)lane_off[K]);
+    LdsReadFrags<0, MI, 32 * BKB>::run(a[K], addr_a + (unsigned)lane_off[K]);
     SlabReads<K + 1, KS, MI, NJ, BKB>::run(a, b, addr_a, addr_b, lane_off);
   }
 };
@@ -373,85 +463,188 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
 #undef IGEMM_STORE
 #undef IGEMM_COMPUTE
 
-  // --- epilogue.  Accumulator element e of lane l in tile (i,j):
-  //     row = wm*WM + i*32 + (e/4)*8 + (l/32)*4 + e%4,  column = wn*WN + j*32 + l%32
-  // Results go through a wave-private LDS staging area (the slab buffers are free now:
-  // the K loop ended on a barrier) so that global stores are 16 bytes wide and each
-  // instruction covers whole row segments.
-  T* __restrict__ Y = (T*)p.y;
-  const int col_lane = lane & 31, row_lane = (lane >> 5) * 4;
-  const bool wide_store = ((p.N * ES) % 16 == 0) && !p.y_aux;
-  T* stage = reinterpret_cast<T*>(smem) + wave * (32 * SW);
-  float s1[NJ], s2[NJ];
-#pragma unroll
-  for (int j = 0; j < NJ; ++j) { s1[j] = 0.0f; s2[j] = 0.0f; }
-  if constexpr (INTERIOR) {
-    float bias[NJ];
-#pragma unroll
-    for (int j = 0; j < NJ; ++j) bias[j] = p.bias ? p.bias[n0 + wn * WN + j * 32 + col_lane] : 0.0f;
-    T* yrow = Y + (m0 + wm * WM) * p.N + n0 + wn * WN;
-    if (p.partial) igemm_store_interior<T, MI, NJ, WN, SW, true, false>(acc, bias, stage, yrow, p.N, lane, s1, s2);
-    else if (p.act == ACT_RELU) igemm_store_interior<T, MI, NJ, WN, SW, false, true>(acc, bias, stage, yrow, p.N, lane, s1, s2);
-    else igemm_store_interior<T, MI, NJ, WN, SW, false, false>(acc, bias, stage, yrow, p.N, lane, s1, s2);
-  } else {
-#pragma unroll
-    for (int i = 0; i < MI; ++i) {
-#pragma unroll
-      for (int j = 0; j < NJ; ++j) {
-        const int col = n0 + wn * WN + j * 32 + col_lane;
-        const bool col_ok = col < p.N;
-        const float bias = (p.bias && col_ok) ? p.bias[col] : 0.0f;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int lr = (e >> 2) * 8 + row_lane + (e & 3);
-          const int64_t m = m0 + wm * WM + i * 32 + lr;
-          const float v = round_to_storage<T>(acc[i][j][e] + bias);   // the stored conv result
-          if (p.partial && m < p.M && col_ok) { s1[j] += v; s2[j] = fmaf(v, v, s2[j]); }
-          const float a = apply_act(v, p.act);
-          if (wide_store) {
-            Store<T>::st(&stage[lr * SW + j * 32 + col_lane], a);
-          } else if (m < p.M && col_ok) {
-            Store<T>::st(&Y[m * p.N + col], a);
-            if (p.y_aux) p.y_aux[m * p.N + col] = a;
-          }
-        }
-      }
-      if (wide_store) {
-        constexpr int EPC = 16 / ES;               // elements per 16-byte chunk
-        constexpr int CPRO = WN / EPC;             // chunks per staged row
-#pragma unroll
-        for (int c = 0; c < (32 * CPRO) / 64; ++c) {
-          const int idx = c * 64 + lane;
-          const int lr = idx / CPRO, ch = idx % CPRO;
-          const int64_t m = m0 + wm * WM + i * 32 + lr;
-          const int col0 = n0 + wn * WN + ch * EPC;
-          if (m < p.M && col0 < p.N)
-            *reinterpret_cast<uint4v*>(Y + m * p.N + col0) = *reinterpret_cast<const uint4v*>(&stage[lr * SW + ch * EPC]);
-        }
-      }
-    }
+  igemm_epilogue<T, BM, BN, WGM, WGN, INTERIOR>(acc, p, smem, sRed, m0, n0, tile_m);
+}
+
+// A-fragment reads of the patch kernel: one address per 32-pixel tile, K-step selected by ^ 32
+template <int I, int N>
+struct Conv3Reads {
+  static __device__ __forceinline__ void run(uint4v (&f)[N], const unsigned (&addr)[N], unsigned kxor) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm volatile("ds_read_b128 %0, %1" : "=v"(f[I]) : "v"(addr[I] ^ kxor));
+#endif
+    Conv3Reads<I + 1, N>::run(f, addr, kxor);
   }
-  if (p.partial) {
+};
+template <int N>
+struct Conv3Reads<N, N> {
+  static __device__ __forceinline__ void run(uint4v (&)[N], const unsigned (&)[N], unsigned) {}
+};
+
+// ---------------------------------------------------------------------------
+// 3x3 convolution with the input patch resident in LDS.
+//
+// The per-tap kernel above fetches every input pixel nine times (once per filter tap) through
+// the vector cache, whose 64 bytes per clock and compute unit then bound the MFMA rate.  Here a
+// workgroup owns TH = 256/W whole image rows (W = image width, a template parameter) and, for
+// each slab of 64 bytes of input channels, loads the (TH+2) x (W+2) patch of pixels around its
+// rows ONCE — zero padding included, delivered by the buffer range check — and forms all nine
+// taps from it: tap (r,s) of pixel (th,tw) is patch cell (th+r, tw+s).  Only the weights
+// (BN rows x 64 bytes per tap) still stream per tap, through a ring of three stages.
+//
+// LDS: the patch is double buffered, cells of 64 bytes stored linearly (the global-to-LDS load
+// writes lane l at base + 16*l), chunk c of cell q in slot c ^ ((q>>2)&3), so that the 16 cells
+// a fragment read touches per pass fall into 16 different 16-byte columns for any tap shift.
+// The K loop runs channel slab outer, tap inner (nine steps, fully unrolled, so that every
+// wait on the load counter is an immediate): step t waits for its own weight loads, the
+// barrier publishes them, then the weight loads of step t+2 and a share of the next slab's
+// patch loads are issued, then 2 x MI x NJ MFMAs.
+// ---------------------------------------------------------------------------
+constexpr int patch_passes(int w) { return (((256 / w + 2) * (w + 2)) * 4 + 255) / 256; }
+// patch passes of the next channel slab issued at tap `tap` (spread over taps 0..6, so that the
+// slab is complete, in load order, before the first weight slab of the next channel slab)
+constexpr int passes_at(int passes, int tap) { return tap < 7 ? passes / 7 + (tap < passes % 7 ? 1 : 0) : 0; }
+constexpr int passes_before(int passes, int tap) {
+  int n = 0;
+  for (int t = 0; t < tap; ++t) n += passes_at(passes, t);
+  return n;
+}
+constexpr int vm_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }   // s_waitcnt vmcnt(n) only
+
+template <typename T, int BN, int WGM, int WGN, int W, bool INTERIOR>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k_conv3_patch(IgemmParams p) {
+  static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
+  constexpr int ES = (int)sizeof(T);
+  constexpr int BM = 256, BKB = 64;
+  constexpr int BK = BKB / ES;
+  constexpr int TH = BM / W, PW = W + 2, PC = (TH + 2) * PW;
+  constexpr int PASSES = patch_passes(W);
+  constexpr int PATCH_BYTES = PASSES * 4096;
+  constexpr int WM = BM / WGM, WN = BN / WGN;
+  constexpr int MI = WM / 32, NJ = WN / 32;
+  constexpr int LB = BN / 64;                   // weight loads per thread and step
+  constexpr int SW = WN + 16 / ES;
+  constexpr int OPER_BYTES = 2 * PATCH_BYTES + 3 * BN * BKB;
+  constexpr int EPI_BYTES = 4 * 32 * SW * ES + WGM * 2 * BN * 4;
+  __shared__ __attribute__((aligned(64))) char smem[OPER_BYTES > EPI_BYTES ? OPER_BYTES : EPI_BYTES];
+  char* const sP = smem;                        // [2][PATCH_BYTES]
+  char* const sB = smem + 2 * PATCH_BYTES;      // [3][BN*BKB]
+  float (*sRed)[2][BN] = reinterpret_cast<float (*)[2][BN]>(smem + 4 * 32 * SW * ES);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+  const int lb = xcd_logical_block((int)blockIdx.x, (int)gridDim.x);
+  const int tile_n = lb % p.tiles_n;
+  const int tile_m = lb / p.tiles_n;
+  const int64_t m0 = (int64_t)tile_m * BM;
+  const int n0 = tile_n * BN;
+  const int tiles_per_img = p.Hc / TH;
+  const int img = tile_m / tiles_per_img;
+  const int h0 = (tile_m - img * tiles_per_img) * TH;
+  const int Hin = p.Hc >> p.up, Win = p.Wc >> p.up;
+  const __amdgpu_buffer_rsrc_t rX = make_rsrc(p.x, p.x_bytes);
+  const __amdgpu_buffer_rsrc_t rW = make_rsrc(p.w, p.w_bytes);
+
+  // patch loader: slot q = pass*256 + tid of the linear patch buffer
+  unsigned a_off[PASSES];
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) {
-      float t1 = s1[j] + __shfl_xor(s1[j], 32, 64);
-      float t2 = s2[j] + __shfl_xor(s2[j], 32, 64);
-      if (lane < 32) {
-        sRed[wm][0][wn * WN + j * 32 + col_lane] = t1;
-        sRed[wm][1][wn * WN + j * 32 + col_lane] = t2;
-      }
-    }
+  for (int i = 0; i < PASSES; ++i) {
+    const int q = i * 256 + tid;
+    const int cell = q >> 2;
+    const int chunk = (q & 3) ^ ((cell >> 2) & 3);
+    const int pr = cell / PW, pc = cell - pr * PW;
+    const int hh = h0 - 1 + pr, ww = pc - 1;
+    const bool ok = cell < PC && hh >= 0 && hh < p.Hc && ww >= 0 && ww < W;
+    const unsigned pix = ((unsigned)img * (unsigned)Hin + (unsigned)(hh >> p.up)) * (unsigned)Win + (unsigned)(ww >> p.up);
+    a_off[i] = ok ? pix * (unsigned)(p.Cin * ES) + (unsigned)chunk * 16u : kOob;
   }
-  if (p.partial) {
-    __syncthreads();
-    for (int i = tid; i < 2 * BN; i += 256) {
-      const int q = i / BN, c = i - q * BN;
-      float t = 0.0f;
+  // weight loader: thread t moves rows t/4 + 64*i, LDS slot t%4
+  const int lrow = tid >> 2;
+  const int gchunk = (tid & 3) ^ ((lrow >> 2) & 3);
+  unsigned b_off[LB];
 #pragma unroll
-      for (int g = 0; g < WGM; ++g) t += sRed[g][q][c];
-      if (n0 + c < p.N) p.partial[(tile_m * 2 + q) * p.N + n0 + c] = t;
-    }
+  for (int i = 0; i < LB; ++i) {
+    const int row = n0 + lrow + i * 64;
+    b_off[i] = row < p.N ? (unsigned)row * (unsigned)(p.K * ES) + (unsigned)gchunk * 16u : kOob;
   }
+  // fragment geometry
+  const int frag_row = lane & 31, fc = lane >> 5;
+  unsigned cell0[MI];                           // patch cell of this lane's pixel for tap (0,0)
+#pragma unroll
+  for (int i = 0; i < MI; ++i) {
+    const int ml = wm * WM + i * 32 + frag_row;
+    cell0[i] = (unsigned)((ml / W) * PW + (ml % W));
+  }
+  const unsigned lds_p = (unsigned)(size_t)(lds_char*)sP;
+  const unsigned lds_b = (unsigned)(size_t)(lds_char*)sB + (unsigned)(wn * WN * BKB) + (unsigned)(frag_row * BKB);
+  const unsigned bsw = (unsigned)((frag_row >> 2) & 3);
+  const unsigned b_lane0 = lds_b + (((unsigned)fc ^ bsw) << 4);          // K-step 0; K-step 1 is ^ 32
+
+  floatx16 acc[MI][NJ];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+  const int NC = (p.Cin * ES) / BKB;            // channel slabs
+  const unsigned tap_bytes = (unsigned)(p.Cin * ES);
+#define PATCH_DMA(BUF, PASS, CBYTE) dma_load16(rX, sP + (BUF) * PATCH_BYTES + (PASS) * 4096 + wave * 1024, a_off[PASS] + (CBYTE))
+#define WEIGHT_DMA(STG, KBYTE)                                                                               \
+  {                                                                                                          \
+    _Pragma("unroll") for (int i = 0; i < LB; ++i)                                                           \
+        dma_load16(rW, sB + (STG) * BN * BKB + i * 4096 + wave * 1024, b_off[i] + (KBYTE));                  \
+  }
+  // prologue: the first patch, the weights of steps 0 and 1
+#pragma unroll
+  for (int i = 0; i < PASSES; ++i) PATCH_DMA(0, i, 0u);
+  WEIGHT_DMA(0, 0u);
+  WEIGHT_DMA(1, tap_bytes);
+
+  // One step: tap TAP of channel slab c.  `last` = this is the last channel slab.
+#define CONV3_STEP(TAP)                                                                                      \
+  {                                                                                                          \
+    constexpr int R_ = (TAP) / 3, S_ = (TAP) % 3;                                                            \
+    constexpr int ALLOWED = LB + passes_at(PASSES, ((TAP) + 7) % 9) + passes_at(PASSES, ((TAP) + 8) % 9);    \
+    if (!last) __builtin_amdgcn_s_waitcnt(vm_imm(ALLOWED));                                                  \
+    else __builtin_amdgcn_s_waitcnt(vm_imm((TAP) < 8 ? LB : 0));                                             \
+    __builtin_amdgcn_s_barrier();                                                                            \
+    uint4v fa[2][MI], fb[2][NJ];                                                                             \
+    unsigned aa[MI];                                                                                         \
+    _Pragma("unroll") for (int i = 0; i < MI; ++i) {                                                         \
+      const unsigned cell = cellb[i] + (unsigned)(R_ * PW + S_);   /* cell index across both buffers */      \
+      aa[i] = lds_p + (cell << 6) + ((((unsigned)fc) ^ ((cell >> 2) & 3u)) << 4);                            \
+    }                                                                                                        \
+    const unsigned bb = b_lane0 + (unsigned)(((TAP) % 3) * BN * BKB);                                        \
+    LdsReadFrags<0, NJ, 32 * BKB>::run(fb[0], bb);                                                           \
+    Conv3Reads<0, MI>::run(fa[0], aa, 0u);                                                                   \
+    LdsReadFrags<0, NJ, 32 * BKB>::run(fb[1], bb ^ 32u);                                                     \
+    Conv3Reads<0, MI>::run(fa[1], aa, 32u);                                                                  \
+    if (!last || (TAP) < 7)                                                                                  \
+      WEIGHT_DMA(((TAP) + 2) % 3, (unsigned)(((TAP) + 2) % 9) * tap_bytes + cbyte + ((TAP) >= 7 ? (unsigned)BKB : 0u)); \
+    if (!last) {                                                                                             \
+      _Pragma("unroll") for (int q = 0; q < passes_at(PASSES, (TAP)); ++q)                                   \
+          PATCH_DMA(nbuf, passes_before(PASSES, (TAP)) + q, cbyte + (unsigned)BKB);                          \
+    }                                                                                                        \
+    SlabSteps<T, 2, 0, MI, NJ>::run(fa, fb, acc);                                                            \
+  }
+
+  for (int c = 0; c < NC; ++c) {
+    const bool last = c + 1 == NC;
+    const int nbuf = (c + 1) & 1;
+    unsigned cellb[MI];                          // the buffer offset is a multiple of 4 cells: the swizzle bits are unchanged
+#pragma unroll
+    for (int i = 0; i < MI; ++i) cellb[i] = cell0[i] + (unsigned)((c & 1) * (PATCH_BYTES / 64));
+    const unsigned cbyte = (unsigned)(c * BKB);
+    CONV3_STEP(0) CONV3_STEP(1) CONV3_STEP(2) CONV3_STEP(3) CONV3_STEP(4)
+    CONV3_STEP(5) CONV3_STEP(6) CONV3_STEP(7) CONV3_STEP(8)
+  }
+#undef CONV3_STEP
+#undef PATCH_DMA
+#undef WEIGHT_DMA
+  __syncthreads();                               // every wave is done with the operands: the epilogue reuses the memory
+  igemm_epilogue<T, BM, BN, WGM, WGN, INTERIOR>(acc, p, smem, sRed, m0, n0, (int64_t)tile_m);
 }
 
 struct IgemmTile { int bm, bn, bkb; };
@@ -479,8 +672,23 @@ bool conv_mfma_supported(const ConvArgs& a) {
   return M * ((a.cout + 63) / 64) / 128 < 0x7FFFFFFF && M < 0x7FFFFFFF;
 }
 
+// The patch kernel takes 3x3 convolutions whose image width is 16..128 (a power of two), whose
+// tiles of 256/W rows divide the image height, with enough tiles to fill the chip, and whose
+// epilogue needs no run-time checks.
+static bool conv3_patch_usable(const ConvArgs& a) {
+  if (a.k != 3 || !conv_mfma_supported(a)) return false;
+  if (a.wc != 16 && a.wc != 32 && a.wc != 64) return false;   // W = 128 needs 96 KB of LDS: one workgroup per compute unit, slower
+  const int th = 256 / a.wc;
+  if (a.hc % th != 0 || a.cout % 64 != 0) return false;
+  const int bn = a.cout % 128 == 0 ? 128 : 64;
+  const int64_t tiles = ((int64_t)a.n * a.hc * a.wc / 256) * (a.cout / bn);
+  if (tiles < 256) return false;
+  return !a.y_aux && a.act != ACT_SIGMOID && !(a.partial && a.act != ACT_NONE);
+}
+
 int conv_partial_rows(const ConvArgs& a, bool mfma) {
   if (!mfma) return kReduceRows;
+  if (conv3_patch_usable(a)) return 256;
   return pick_tile((int64_t)a.n * a.hc * a.wc, a.cout, a.cin, (int)dtype_size(a.dtype)).bm;
 }
 
@@ -494,6 +702,27 @@ int launch_conv_mfma(const ConvArgs& a, hipStream_t s) {
   p.Hc = a.hc; p.Wc = a.wc; p.Cin = a.cin; p.ksz = a.k; p.up = a.up; p.act = a.act;
   p.x_bytes = (unsigned)((int64_t)a.n * (a.hc >> a.up) * (a.wc >> a.up) * a.cin * es);
   p.w_bytes = (unsigned)((int64_t)a.cout * a.k * a.k * a.cin * es);
+  if (conv3_patch_usable(a)) {
+    const int bn = a.cout % 128 == 0 ? 128 : 64;
+    p.tiles_n = a.cout / bn;
+    dim3 pgrid((unsigned)((p.M / 256) * p.tiles_n));
+#define PATCH_LAUNCH_W(T, WV)                                                                             \
+  do {                                                                                                   \
+    if (bn == 128) hipLaunchKernelGGL((k_conv3_patch<T, 128, 2, 2, WV, true>), pgrid, dim3(256), 0, s, p); \
+    else hipLaunchKernelGGL((k_conv3_patch<T, 64, 4, 1, WV, true>), pgrid, dim3(256), 0, s, p);           \
+  } while (0)
+#define PATCH_LAUNCH(T)                                     \
+  do {                                                      \
+    if (a.wc == 16) PATCH_LAUNCH_W(T, 16);                  \
+    else if (a.wc == 32) PATCH_LAUNCH_W(T, 32);             \
+    else PATCH_LAUNCH_W(T, 64);                             \
+  } while (0)
+    if (a.dtype == AE_BF16) PATCH_LAUNCH(bf16_t);
+    else PATCH_LAUNCH(float);
+#undef PATCH_LAUNCH
+#undef PATCH_LAUNCH_W
+    return launch_status("conv3_patch");
+  }
   const IgemmTile t = pick_tile(p.M, a.cout, a.cin, es);
   p.tiles_n = (a.cout + t.bn - 1) / t.bn;
   const int64_t tiles_m = (p.M + t.bm - 1) / t.bm;
