@@ -105,9 +105,14 @@ int forward_conv(ae_model* m, int si, Step& st, const float* params, const void*
   const double in_el = (double)P.batch * st.cin * st.hin * st.win, raw_el = (double)rows * st.cout;
   const double out_el = (double)P.batch * st.cout * st.hout * st.wout;
   if (st.thin == 2) {
-    TIMED(si, "fwd.conv_thin_out", 2.0 * raw_el * st.cin * st.k * st.k, (in_el + raw_el) * es,
-          launch_thin_out_conv(in, params + st.w_off, params + st.b_off, st.out, st.aux, P.batch, st.hc, st.wc, st.cout,
-                               st.cin, st.up, st.act, P.dtype, s));
+    if (thin_out_mfma_supported(st.cout, st.cin, st.k, P.dtype))
+      TIMED(si, "fwd.conv_thin_out_mfma", 2.0 * raw_el * st.cin * st.k * st.k, (in_el + raw_el) * es,
+            launch_thin_out_mfma(in, params + st.w_off, st.wpack, params + st.b_off, st.out, st.aux, P.batch, st.hc,
+                                 st.wc, st.cout, st.cin, st.up, st.act, s));
+    else
+      TIMED(si, "fwd.conv_thin_out", 2.0 * raw_el * st.cin * st.k * st.k, (in_el + raw_el) * es,
+            launch_thin_out_conv(in, params + st.w_off, params + st.b_off, st.out, st.aux, P.batch, st.hc, st.wc, st.cout,
+                                 st.cin, st.up, st.act, P.dtype, s));
     return AE_OK;
   }
   const void* w = nullptr;
@@ -221,7 +226,8 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
     // dr is planar [n][C_out][H][W]
     TIMED(si, "bwd.bias_planesum", 0.0, raw_el * es,
           launch_plane_sums(dr, P.batch, st.cout, (int64_t)st.hc * st.wc, P.dtype, m->partial, s));
-    TIMED(si, "bwd.bias_finalize", 0.0, 0.0, launch_colsum_finalize(m->partial, P.batch, st.cout, grads + st.b_off, s));
+    TIMED(si, "bwd.bias_finalize", 0.0, 0.0,
+          launch_colsum_finalize(m->partial, P.batch * plane_sums_split((int64_t)st.hc * st.wc), st.cout, grads + st.b_off, s));
     if (thin_wgrad_mfma_supported(st.cout, st.cin, st.win, P.dtype))
       TIMED(si, "bwd.wgrad_thin_mfma", conv_flops, (in_el + raw_el) * es + wel * 4,
             launch_thin_wgrad_mfma(dr, in, m->wgrad_ws, grads + st.w_off, P.batch, st.hin, st.win, st.cout, st.cin, 1,

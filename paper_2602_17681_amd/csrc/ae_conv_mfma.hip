@@ -466,6 +466,23 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   igemm_epilogue<T, BM, BN, WGM, WGN, INTERIOR>(acc, p, smem, sRed, m0, n0, tile_m);
 }
 
+// wait until at most N LDS reads are outstanding, then hand the fragments to the compiler
+template <int N, int MI, int NJ>
+__device__ __forceinline__ void lds_wait_tie(uint4v (&a)[MI], uint4v (&b)[NJ]) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N));
+#endif
+  TieFrags<0, MI>::run(a);
+  TieFrags<0, NJ>::run(b);
+}
+template <typename T, int MI, int NJ>
+__device__ __forceinline__ void mma_group(const uint4v (&a)[MI], const uint4v (&b)[NJ], floatx16 (&acc)[MI][NJ]) {
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) mma_step<T>(a[i], b[j], acc[i][j]);
+}
+
 // A-fragment reads of the patch kernel: one address per 32-pixel tile, K-step selected by ^ 32
 template <int I, int N>
 struct Conv3Reads {
@@ -596,50 +613,77 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
     _Pragma("unroll") for (int i = 0; i < LB; ++i)                                                           \
         dma_load16(rW, sB + (STG) * BN * BKB + i * 4096 + wave * 1024, b_off[i] + (KBYTE));                  \
   }
-  // prologue: the first patch, the weights of steps 0 and 1
+  // Fragment registers: set 0 holds K-step 0 of the current tap (read during the previous step),
+  // set 1 K-step 1 (read at the start of the step, behind the MFMAs of K-step 0); while the
+  // MFMAs of K-step 1 run, set 0 is refilled for the next tap.  The weights of step t+1 are
+  // therefore required (own loads done, then barrier) already at the start of step t.
+  uint4v f0a[MI], f0b[NJ], f1a[MI], f1b[NJ];
+#define CONV3_ADDR(AA, CELLS, TAPV)                                                                          \
+  _Pragma("unroll") for (int i = 0; i < MI; ++i) {                                                           \
+    const unsigned cell = CELLS[i] + (unsigned)(((TAPV) / 3) * PW + (TAPV) % 3);                             \
+    AA[i] = lds_p + (cell << 6) + ((((unsigned)fc) ^ ((cell >> 2) & 3u)) << 4);                              \
+  }
+  // prologue: the first patch, the weights of steps 0 and 1; fragments of (slab 0, tap 0, K-step 0)
 #pragma unroll
   for (int i = 0; i < PASSES; ++i) PATCH_DMA(0, i, 0u);
   WEIGHT_DMA(0, 0u);
   WEIGHT_DMA(1, tap_bytes);
+  __builtin_amdgcn_s_waitcnt(vm_imm(LB));
+  __builtin_amdgcn_s_barrier();
+  {
+    unsigned aa[MI];
+    CONV3_ADDR(aa, cell0, 0)
+    LdsReadFrags<0, NJ, 32 * BKB>::run(f0b, b_lane0);
+    Conv3Reads<0, MI>::run(f0a, aa, 0u);
+  }
 
   // One step: tap TAP of channel slab c.  `last` = this is the last channel slab.
 #define CONV3_STEP(TAP)                                                                                      \
   {                                                                                                          \
-    constexpr int R_ = (TAP) / 3, S_ = (TAP) % 3;                                                            \
-    constexpr int ALLOWED = LB + passes_at(PASSES, ((TAP) + 7) % 9) + passes_at(PASSES, ((TAP) + 8) % 9);    \
-    if (!last) __builtin_amdgcn_s_waitcnt(vm_imm(ALLOWED));                                                  \
-    else __builtin_amdgcn_s_waitcnt(vm_imm((TAP) < 8 ? LB : 0));                                             \
+    if (!last) __builtin_amdgcn_s_waitcnt(vm_imm(passes_at(PASSES, ((TAP) + 8) % 9)));                       \
+    else __builtin_amdgcn_s_waitcnt(vm_imm(0));                                                              \
     __builtin_amdgcn_s_barrier();                                                                            \
-    uint4v fa[2][MI], fb[2][NJ];                                                                             \
-    unsigned aa[MI];                                                                                         \
-    _Pragma("unroll") for (int i = 0; i < MI; ++i) {                                                         \
-      const unsigned cell = cellb[i] + (unsigned)(R_ * PW + S_);   /* cell index across both buffers */      \
-      aa[i] = lds_p + (cell << 6) + ((((unsigned)fc) ^ ((cell >> 2) & 3u)) << 4);                            \
-    }                                                                                                        \
-    const unsigned bb = b_lane0 + (unsigned)(((TAP) % 3) * BN * BKB);                                        \
-    LdsReadFrags<0, NJ, 32 * BKB>::run(fb[0], bb);                                                           \
-    Conv3Reads<0, MI>::run(fa[0], aa, 0u);                                                                   \
-    LdsReadFrags<0, NJ, 32 * BKB>::run(fb[1], bb ^ 32u);                                                     \
-    Conv3Reads<0, MI>::run(fa[1], aa, 32u);                                                                  \
     if (!last || (TAP) < 7)                                                                                  \
       WEIGHT_DMA(((TAP) + 2) % 3, (unsigned)(((TAP) + 2) % 9) * tap_bytes + cbyte + ((TAP) >= 7 ? (unsigned)BKB : 0u)); \
     if (!last) {                                                                                             \
       _Pragma("unroll") for (int q = 0; q < passes_at(PASSES, (TAP)); ++q)                                   \
           PATCH_DMA(nbuf, passes_before(PASSES, (TAP)) + q, cbyte + (unsigned)BKB);                          \
     }                                                                                                        \
-    SlabSteps<T, 2, 0, MI, NJ>::run(fa, fb, acc);                                                            \
+    {                                                                                                        \
+      unsigned aa[MI];                                                                                       \
+      CONV3_ADDR(aa, cellb, (TAP))                                                                           \
+      LdsReadFrags<0, NJ, 32 * BKB>::run(f1b, (b_lane0 + (unsigned)(((TAP) % 3) * BN * BKB)) ^ 32u);         \
+      Conv3Reads<0, MI>::run(f1a, aa, 32u);                                                                  \
+    }                                                                                                        \
+    lds_wait_tie<MI + NJ, MI, NJ>(f0a, f0b);                                                                 \
+    mma_group<T, MI, NJ>(f0a, f0b, acc);                                                                     \
+    __builtin_amdgcn_sched_barrier(0);                                                                       \
+    lds_wait_tie<0, MI, NJ>(f1a, f1b);                                                                       \
+    if (!(last && (TAP) == 8)) {                                                                             \
+      unsigned aa[MI];                                                                                       \
+      if ((TAP) == 8) { CONV3_ADDR(aa, celln, 0) } else { CONV3_ADDR(aa, cellb, ((TAP) + 1) % 9) }           \
+      LdsReadFrags<0, NJ, 32 * BKB>::run(f0b, b_lane0 + (unsigned)((((TAP) + 1) % 3) * BN * BKB));           \
+      Conv3Reads<0, MI>::run(f0a, aa, 0u);                                                                   \
+    }                                                                                                        \
+    __builtin_amdgcn_sched_barrier(0);                                                                       \
+    mma_group<T, MI, NJ>(f1a, f1b, acc);                                                                     \
+    __builtin_amdgcn_sched_barrier(0);                                                                       \
   }
 
   for (int c = 0; c < NC; ++c) {
     const bool last = c + 1 == NC;
     const int nbuf = (c + 1) & 1;
-    unsigned cellb[MI];                          // the buffer offset is a multiple of 4 cells: the swizzle bits are unchanged
+    unsigned cellb[MI], celln[MI];               // the buffer offset is a multiple of 4 cells: the swizzle bits are unchanged
 #pragma unroll
-    for (int i = 0; i < MI; ++i) cellb[i] = cell0[i] + (unsigned)((c & 1) * (PATCH_BYTES / 64));
+    for (int i = 0; i < MI; ++i) {
+      cellb[i] = cell0[i] + (unsigned)((c & 1) * (PATCH_BYTES / 64));
+      celln[i] = cell0[i] + (unsigned)(nbuf * (PATCH_BYTES / 64));
+    }
     const unsigned cbyte = (unsigned)(c * BKB);
     CONV3_STEP(0) CONV3_STEP(1) CONV3_STEP(2) CONV3_STEP(3) CONV3_STEP(4)
     CONV3_STEP(5) CONV3_STEP(6) CONV3_STEP(7) CONV3_STEP(8)
   }
+#undef CONV3_ADDR
 #undef CONV3_STEP
 #undef PATCH_DMA
 #undef WEIGHT_DMA

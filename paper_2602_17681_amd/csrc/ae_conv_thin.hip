@@ -313,18 +313,38 @@ __global__ void k_thin_wgrad_reduce(const float* __restrict__ partial, int nbloc
   }
 }
 
-// per-plane sums of a planar tensor [n][C][HW]: partial[n][0][c] = sum, partial[n][1][c] = sum of squares
+// per-plane sums of a planar tensor [n][C][HW], each plane cut into `split` pieces:
+// partial[(n*split + piece)][0][c] = sum, [..][1][c] = sum of squares
 template <typename T>
-__global__ void k_plane_sums(const T* __restrict__ x, int C, int64_t HW, float* __restrict__ partial) {
+__global__ void k_plane_sums(const T* __restrict__ x, int C, int64_t HW, int split, int vec, float* __restrict__ partial) {
   __shared__ float sm[NT / 64 + 1];
+  constexpr int V = Store<T>::VEC;
+  const int piece = blockIdx.y;
   const int c = blockIdx.x % C;
   const int64_t n = blockIdx.x / C;
+  const int64_t len = (HW + split - 1) / split;
+  const int64_t i0 = piece * len, i1 = i0 + len < HW ? i0 + len : HW;
   const T* p = x + (n * C + c) * HW;
   float s1 = 0.0f, s2 = 0.0f;
-  for (int64_t i = threadIdx.x; i < HW; i += NT) { const float v = Store<T>::ld(p + i); s1 += v; s2 = fmaf(v, v, s2); }
+  int64_t i = i0 + threadIdx.x;
+  if (vec && len % V == 0) {                     // pieces start on 16-byte boundaries
+#pragma unroll 4
+    for (int64_t q = i0 + (int64_t)threadIdx.x * V; q + V <= i1; q += (int64_t)NT * V) {
+      float v[V];
+      Store<T>::ldv(p + q, v);
+#pragma unroll
+      for (int j = 0; j < V; ++j) { s1 += v[j]; s2 = fmaf(v[j], v[j], s2); }
+    }
+    i = i0 + (i1 - i0) / V * V + threadIdx.x;
+  }
+  for (; i < i1; i += NT) { const float v = Store<T>::ld(p + i); s1 += v; s2 = fmaf(v, v, s2); }
   s1 = block_sum<NT>(s1, sm);
   s2 = block_sum<NT>(s2, sm);
-  if (threadIdx.x == 0) { partial[(n * 2) * C + c] = s1; partial[(n * 2 + 1) * C + c] = s2; }
+  if (threadIdx.x == 0) {
+    const int64_t row = n * split + piece;
+    partial[(row * 2) * C + c] = s1;
+    partial[(row * 2 + 1) * C + c] = s2;
+  }
 }
 
 }  // namespace
@@ -420,12 +440,23 @@ int launch_thin_wgrad(const void* thin, const void* wide, float* workspace, floa
   return launch_status("thin_wgrad_reduce");
 }
 
+int plane_sums_split(int64_t hw) {
+  int split = (int)(hw / 8192);                  // about 8192 elements per workgroup
+  if (split < 1) split = 1;
+  if (split > 64) split = 64;
+  return split;
+}
+
+// writes n*plane_sums_split(hw) partial rows
 int launch_plane_sums(const void* x, int64_t n, int c, int64_t hw, int dtype, float* partial, hipStream_t s) {
   if (n * c > 0x7FFFFFFF) return fail(AE_EINVAL, "plane_sums: too many planes");
+  const int split = plane_sums_split(hw);
+  const int vec = (((uintptr_t)x & 15) == 0 && hw % 8 == 0) ? 1 : 0;
+  dim3 grid((unsigned)(n * c), (unsigned)split);
   if (dtype == AE_BF16)
-    hipLaunchKernelGGL((k_plane_sums<bf16_t>), dim3((unsigned)(n * c)), dim3(NT), 0, s, (const bf16_t*)x, c, hw, partial);
+    hipLaunchKernelGGL((k_plane_sums<bf16_t>), grid, dim3(NT), 0, s, (const bf16_t*)x, c, hw, split, vec, partial);
   else
-    hipLaunchKernelGGL((k_plane_sums<float>), dim3((unsigned)(n * c)), dim3(NT), 0, s, (const float*)x, c, hw, partial);
+    hipLaunchKernelGGL((k_plane_sums<float>), grid, dim3(NT), 0, s, (const float*)x, c, hw, split, vec, partial);
   return launch_status("plane_sums");
 }
 

@@ -447,11 +447,132 @@ __global__ void k_thin_wgrad_mfma_reduce(const float* __restrict__ partial, int 
   }
 }
 
+// ---------------------------------------------------------------------------
+// thin-out conv (forward of the last layer, optionally through the x2 upsample):
+//   out[n][ct][y][x] = act( b[ct] + sum_{r,s,cw} wide[n][(y+r-1)>>up][(x+s-1)>>up][cw] * W[ct][cw][r][s] )
+// as a small GEMM followed by a shifted sum.  For every wide pixel q of a patch (TH x TW pixels
+// plus a halo of one) the matrix cores compute
+//   Z[q][tap*CT + ct] = sum_cw wide[q][cw] * W[ct][cw][tap]          (N = 9*CT columns, padded to 32*NJ)
+// reading each wide pixel once, straight from global memory into the MFMA operand layout (lane l:
+// pixel l%32, 8 channels at 16*ks + 8*(l/32)); Z goes to LDS as fp32, and every output pixel then
+// adds its nine terms Z[pixel under tap (r,s)][(r,s),ct] in a fixed order.
+// wz: bf16 [32*NJ][CW], row tap*CT + ct (zero rows beyond 9*CT).  out planar (+ optional fp32 copy).
+// ---------------------------------------------------------------------------
+__global__ void k_thin_pack_wz(const float* __restrict__ wcanon, bf16_t* __restrict__ wz, int CT, int CW, int rows) {
+  const int i = blockIdx.x * NT + threadIdx.x;
+  if (i >= rows * CW) return;
+  const int cw = i % CW, col = i / CW;
+  float v = 0.0f;
+  if (col < 9 * CT) {
+    const int ct = col % CT, tap = col / CT;
+    v = wcanon[((int64_t)ct * CW + cw) * 9 + tap];
+  }
+  wz[i] = f32_to_bf16(v);
+}
+
+template <int NJ, int KS>   // 32*NJ >= 9*CT columns, CW = 16*KS wide channels
+__global__ __launch_bounds__(NT) void k_thin_out_mfma(const bf16_t* __restrict__ wide, const bf16_t* __restrict__ wz,
+                                                      const float* __restrict__ bias, bf16_t* __restrict__ out,
+                                                      float* __restrict__ out_f32, int Hq, int Wq, int CT, int up,
+                                                      int act, int TW, int tw_shift, int tiles_w, int tiles_h) {
+  constexpr int CW = 16 * KS;
+  constexpr int ZS = 32 * NJ + 1;               // odd row stride: conflict-free column reads
+  constexpr int MAXC = 352;                     // (TH+2)*(TW+2) <= 340 cells for TW in {8,16,32}, rounded up to 32
+  constexpr int TPW = 3;                        // row tiles of 32 cells per wave (11 tiles over 4 waves)
+  __shared__ float sZ[MAXC * ZS];
+  const int TH = NT >> tw_shift;
+  const int PW = TW + 2, cells = (TH + 2) * PW;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int b = blockIdx.x;
+  const int tx = b % tiles_w; b /= tiles_w;
+  const int ty = b % tiles_h;
+  const int n = b / tiles_h;
+  const int h0 = ty * TH, w0 = tx * TW;        // wide coordinates
+  const int frag_row = lane & 31, g = lane >> 5;
+
+  // all global loads of the wave's row tiles first
+  uint4 av[TPW][KS];
+#pragma unroll
+  for (int t = 0; t < TPW; ++t) {
+    const int cell = (wave + 4 * t) * 32 + frag_row;
+    const int pr = cell / PW, pc = cell - pr * PW;
+    const int hh = h0 - 1 + pr, ww = w0 - 1 + pc;
+    const bool ok = cell < cells && hh >= 0 && hh < Hq && ww >= 0 && ww < Wq;
+    const bf16_t* src = wide + (((int64_t)n * Hq + min(max(hh, 0), Hq - 1)) * Wq + min(max(ww, 0), Wq - 1)) * CW + g * 8;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      av[t][ks] = *reinterpret_cast<const uint4*>(src + ks * 16);
+      if (!ok) { av[t][ks].x = 0u; av[t][ks].y = 0u; av[t][ks].z = 0u; av[t][ks].w = 0u; }
+    }
+  }
+  t_bf16x8 bw[KS][NJ];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+      bw[ks][j] = *reinterpret_cast<const t_bf16x8*>(&wz[(j * 32 + frag_row) * CW + ks * 16 + g * 8]);
+
+#pragma unroll
+  for (int t = 0; t < TPW; ++t) {
+    const int rt = wave + 4 * t;
+    if (rt * 32 < cells) {                      // uniform per wave
+      t_floatx16 acc[NJ];
+#pragma unroll
+      for (int j = 0; j < NJ; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[j][e] = 0.0f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        union { uint4 u; t_bf16x8 v; } a;
+        a.u = av[t][ks];
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, bw[ks][j], acc[j], 0, 0, 0);
+      }
+#pragma unroll
+      for (int j = 0; j < NJ; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int row = rt * 32 + (e >> 2) * 8 + g * 4 + (e & 3);
+          sZ[row * ZS + j * 32 + frag_row] = acc[j][e];
+        }
+    }
+  }
+  __syncthreads();
+
+  // shifted sums: item -> (ct, y, x) of the output patch, x fastest (planar rows are contiguous)
+  const int Hc = Hq << up, Wc = Wq << up;
+  const int OW = TW << up, OH = TH << up;
+  const int ow_shift = tw_shift + up;
+  const int64_t HWc = (int64_t)Hc * Wc;
+  for (int item = tid; item < CT * OH * OW; item += NT) {
+    const int xl = item & (OW - 1), rr = item >> ow_shift;
+    const int yl = rr & (OH - 1), ct = rr / OH;
+    const int y = (h0 << up) + yl, x = (w0 << up) + xl;
+    if (y < Hc && x < Wc) {
+      float v = bias ? bias[ct] : 0.0f;
+#pragma unroll
+      for (int r = 0; r < 3; ++r) {
+        const int yy = y + r - 1;
+        const int prow = ((yy >> up) - (h0 - 1)) * PW;
+#pragma unroll
+        for (int s_ = 0; s_ < 3; ++s_) {
+          const int xx = x + s_ - 1;
+          if (yy >= 0 && yy < Hc && xx >= 0 && xx < Wc) v += sZ[(prow + (xx >> up) - (w0 - 1)) * ZS + (r * 3 + s_) * CT + ct];
+        }
+      }
+      const float a = apply_act(bf16_to_f32(f32_to_bf16(v)), act);
+      const int64_t o = ((int64_t)n * CT + ct) * HWc + (int64_t)y * Wc + x;
+      out[o] = f32_to_bf16(a);
+      if (out_f32) out_f32[o] = a;
+    }
+  }
+}
+
 struct ThinTile { int tw, shift, th, tiles_w, tiles_h, blocks; };
-ThinTile thin_tile(int n, int h, int w) {
+ThinTile thin_tile(int n, int h, int w, int max_tw = 64) {
   ThinTile t;
   t.tw = 8; t.shift = 3;
-  while (t.tw < 64 && t.tw < w) { t.tw <<= 1; ++t.shift; }
+  while (t.tw < max_tw && t.tw < w) { t.tw <<= 1; ++t.shift; }
   t.th = NT / t.tw;
   t.tiles_w = (w + t.tw - 1) / t.tw;
   t.tiles_h = (h + t.th - 1) / t.th;
@@ -498,6 +619,38 @@ int launch_thin_in_mfma(const void* thin, const float* wcanon, void* wfrag, cons
 #undef LAUNCH_TIM_NJ
 #undef LAUNCH_TIM
   return launch_status("thin_in_mfma");
+}
+
+bool thin_out_mfma_supported(int ct, int cw, int k, int dtype) {
+  return dtype == AE_BF16 && k == 3 && ct >= 1 && ct <= 4 && (cw == 32 || cw == 64 || cw == 128);
+}
+
+int64_t thin_out_wz_bytes(int ct, int cw) { return (int64_t)((9 * ct + 31) / 32) * 32 * cw * 2; }
+
+// wide: [n*hq*wq][cw] (hq = hc >> up); out: planar [n][ct][hc][wc] (+ fp32 copy); wz: scratch of thin_out_wz_bytes
+int launch_thin_out_mfma(const void* wide, const float* wcanon, void* wz, const float* bias, void* out, float* out_f32,
+                         int n, int hc, int wc, int ct, int cw, int up, int act, hipStream_t s) {
+  if (!thin_out_mfma_supported(ct, cw, 3, AE_BF16) || up < 0 || up > 1) return fail(AE_EINVAL, "thin_out_mfma: shape not supported");
+  if (((uintptr_t)wide & 15) != 0) return fail(AE_EINVAL, "thin_out_mfma: input must be 16-byte aligned");
+  const int hq = hc >> up, wq = wc >> up;
+  const ThinTile t = thin_tile(n, hq, wq, 32);  // squarer patches: less halo
+  const int nj = (9 * ct + 31) / 32;
+  hipLaunchKernelGGL(k_thin_pack_wz, dim3((unsigned)((nj * 32 * cw + NT - 1) / NT)), dim3(NT), 0, s, wcanon, (bf16_t*)wz, ct,
+                     cw, nj * 32);
+  AE_TRY(launch_status("thin_pack_wz"));
+#define LAUNCH_TOM(NJV, KSV)                                                                                     \
+  hipLaunchKernelGGL((k_thin_out_mfma<NJV, KSV>), dim3((unsigned)t.blocks), dim3(NT), 0, s, (const bf16_t*)wide, \
+                     (const bf16_t*)wz, bias, (bf16_t*)out, out_f32, hq, wq, ct, up, act, t.tw, t.shift, t.tiles_w, t.tiles_h)
+#define LAUNCH_TOM_KS(NJV)                   \
+  switch (cw) {                              \
+    case 32: LAUNCH_TOM(NJV, 2); break;      \
+    case 64: LAUNCH_TOM(NJV, 4); break;      \
+    default: LAUNCH_TOM(NJV, 8); break;      \
+  }
+  if (nj == 1) { LAUNCH_TOM_KS(1) } else { LAUNCH_TOM_KS(2) }
+#undef LAUNCH_TOM_KS
+#undef LAUNCH_TOM
+  return launch_status("thin_out_mfma");
 }
 
 bool thin_wgrad_mfma_supported(int ct, int cw, int wq, int dtype) {

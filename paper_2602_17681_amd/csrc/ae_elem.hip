@@ -461,13 +461,25 @@ __global__ void k_fill_zero(uint32_t* p, int64_t n_words) {
   for (int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x; i < n_words; i += (int64_t)gridDim.x * NT) p[i] = 0u;
 }
 
-// loss += sum((y-t)^2)/n over the block's slice; dy = 2 (y-t)/n
+// loss += sum((y-t)^2)/n over the block's slice; dy = 2 (y-t)/n.  16 bytes per thread and
+// access when the tensors allow it (vec), several independent accesses in flight.
 template <typename T>
 __global__ void k_mse(const T* __restrict__ y, const T* __restrict__ t, int64_t n, float inv_n, float* __restrict__ loss,
-                      T* __restrict__ dy) {
+                      T* __restrict__ dy, int vec) {
   __shared__ float sm[NT / 64 + 1];
+  constexpr int V = Store<T>::VEC;
   float acc = 0.0f;
-  for (int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x; i < n; i += (int64_t)gridDim.x * NT) {
+  const int64_t nv = vec ? n / V : 0;
+#pragma unroll 4
+  for (int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x; i < nv; i += (int64_t)gridDim.x * NT) {
+    float a[V], b[V], d[V];
+    Store<T>::ldv(y + i * V, a);
+    Store<T>::ldv(t + i * V, b);
+#pragma unroll
+    for (int j = 0; j < V; ++j) { d[j] = a[j] - b[j]; acc = fmaf(d[j], d[j], acc); d[j] = 2.0f * d[j] * inv_n; }
+    if (dy) Store<T>::stv(dy + i * V, d);
+  }
+  for (int64_t i = nv * V + (int64_t)blockIdx.x * NT + threadIdx.x; i < n; i += (int64_t)gridDim.x * NT) {
     float d = Store<T>::ld(y + i) - Store<T>::ld(t + i);
     acc = fmaf(d, d, acc);
     if (dy) Store<T>::st(dy + i, 2.0f * d * inv_n);
@@ -619,8 +631,9 @@ int launch_fill_zero(void* p, int64_t bytes, hipStream_t s) {
 
 int launch_mse(const void* y, const void* t, int64_t n, int dtype, float* loss, void* dy, hipStream_t s) {
   AE_TRY(launch_fill_zero(loss, 4, s));
-  DISPATCH_T(dtype, hipLaunchKernelGGL((k_mse<T>), dim3(grid_for(n, NT * 8, 2048)), dim3(NT), 0, s, (const T*)y,
-                                       (const T*)t, n, (float)(1.0 / (double)n), loss, (T*)dy));
+  const int vec = (((uintptr_t)y | (uintptr_t)t | (uintptr_t)dy) & 15) == 0 ? 1 : 0;
+  DISPATCH_T(dtype, hipLaunchKernelGGL((k_mse<T>), dim3(grid_for(n, NT * 16, 4096)), dim3(NT), 0, s, (const T*)y,
+                                       (const T*)t, n, (float)(1.0 / (double)n), loss, (T*)dy, vec));
   return launch_status("mse");
 }
 

@@ -146,6 +146,10 @@ int thin_in_mfma_blocks(int n, int h, int w);   // = number of partial-sum block
 int64_t thin_wfrag_bytes(int cw);               // scratch for the repacked weights
 int launch_thin_in_mfma(const void* thin, const float* wcanon, void* wfrag, const float* bias, void* out, float* partial,
                         int n, int h, int w, int ct, int cw, int flip, int act, int upsum, hipStream_t s);
+bool thin_out_mfma_supported(int ct, int cw, int k, int dtype);
+int64_t thin_out_wz_bytes(int ct, int cw);
+int launch_thin_out_mfma(const void* wide, const float* wcanon, void* wz, const float* bias, void* out, float* out_f32,
+                         int n, int hc, int wc, int ct, int cw, int up, int act, hipStream_t s);
 bool thin_wgrad_mfma_supported(int ct, int cw, int wq, int dtype);
 int64_t thin_wgrad_mfma_workspace_floats(int n, int hq, int wq, int cw);
 int launch_thin_wgrad_mfma(const void* thin, const void* wide, float* workspace, float* dw_canonical, int n, int hq,
@@ -153,6 +157,7 @@ int launch_thin_wgrad_mfma(const void* thin, const void* wide, float* workspace,
 int64_t thin_wgrad_workspace_floats(int64_t q_pixels, int ct, int cw);
 int launch_thin_wgrad(const void* thin, const void* wide, float* workspace, float* dw_canonical, int n, int hq, int wq,
                       int ct, int cw, int mode, int up, int dtype, hipStream_t s);
+int plane_sums_split(int64_t hw);   // pieces per plane = partial rows per sample
 int launch_plane_sums(const void* x, int64_t n, int c, int64_t hw, int dtype, float* partial, hipStream_t s);
 
 // per-channel reductions and the second pass after a conv

@@ -115,15 +115,22 @@ template <> __device__ __forceinline__ void st4<bf16_t>(bf16_t* p, const float (
   *reinterpret_cast<uint2*>(p) = t;
 }
 
-// One wavefront per sample.  FLAT: the sample is a contiguous vector of n = C
+// One wavefront per sample (TPS = 64) or, for small batches, one workgroup per sample (TPS = 256).  FLAT: the sample is a contiguous vector of n = C
 // elements with n % 4 == 0 (16-byte / 8-byte vector access).  Otherwise the sample
 // is stored [HW][C] and element i = c*HW + hw of the (c,h,w) order is gathered.
-template <typename T, bool FLAT>
+template <int TPS>
+__device__ __forceinline__ float sample_sum(float v, float* sm) {
+  if (TPS == 64) return wave_sum(v);
+  return block_sum<NT>(v, sm);
+}
+
+template <typename T, bool FLAT, int TPS>
 __global__ void k_pnorm_awgn(const T* __restrict__ z, T* __restrict__ y, int64_t batch, int C, int HW, int do_pnorm,
                              int do_awgn, float sigma, uint64_t seed, uint64_t first_sample) {
-  const int lane = threadIdx.x & 63;
-  const int64_t b = (int64_t)blockIdx.x * (NT / 64) + (threadIdx.x >> 6);
-  if (b >= batch) return;
+  __shared__ float sm[NT / 64 + 1];
+  const int lane = threadIdx.x % TPS;
+  const int64_t b = (int64_t)blockIdx.x * (NT / TPS) + (threadIdx.x / TPS);
+  if (b >= batch) return;                        // whole wavefronts (TPS = 64) or never (TPS = 256: grid = batch)
   const int64_t n = (int64_t)C * HW;
   const T* zb = z + b * n;
   T* yb = y + b * n;
@@ -132,20 +139,22 @@ __global__ void k_pnorm_awgn(const T* __restrict__ z, T* __restrict__ y, int64_t
   if (do_pnorm) {
     float ss = 0.0f;
     if (FLAT) {
-      for (int64_t q = lane; q < nquads; q += 64) {
+#pragma unroll 4
+      for (int64_t q = lane; q < nquads; q += TPS) {
         float v[4];
         ld4<T>(zb + 4 * q, v);
         ss = fmaf(v[0], v[0], ss); ss = fmaf(v[1], v[1], ss); ss = fmaf(v[2], v[2], ss); ss = fmaf(v[3], v[3], ss);
       }
     } else {
-      for (int64_t i = lane; i < n; i += 64) { float v = Store<T>::ld(zb + i); ss = fmaf(v, v, ss); }
+#pragma unroll 8
+      for (int64_t i = lane; i < n; i += TPS) { float v = Store<T>::ld(zb + i); ss = fmaf(v, v, ss); }
     }
-    ss = wave_sum(ss);
+    ss = sample_sum<TPS>(ss, sm);
     const float ms = ss / (float)n;
     scale = ms > 0.0f ? 1.0f / sqrtf(ms) : 0.0f;
   }
   const uint64_t sample = first_sample + (uint64_t)b;
-  for (int64_t q = lane; q < nquads; q += 64) {
+  for (int64_t q = lane; q < nquads; q += TPS) {
     float g[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     if (do_awgn) {
       normal_quad(seed, sample, (uint32_t)q, g);
@@ -173,29 +182,32 @@ __global__ void k_pnorm_awgn(const T* __restrict__ z, T* __restrict__ y, int64_t
 }
 
 // x = z/r: dz = g/r - z * sum(g z) / (n r^3); elementwise in storage order
-template <typename T>
+template <typename T, int TPS>
 __global__ void k_pnorm_bwd(const T* __restrict__ z, const T* __restrict__ g, T* __restrict__ dz, int64_t batch,
                             int64_t n) {
-  const int lane = threadIdx.x & 63;
-  const int64_t b = (int64_t)blockIdx.x * (NT / 64) + (threadIdx.x >> 6);
+  __shared__ float sm[NT / 64 + 1];
+  const int lane = threadIdx.x % TPS;
+  const int64_t b = (int64_t)blockIdx.x * (NT / TPS) + (threadIdx.x / TPS);
   if (b >= batch) return;
   const T* zb = z + b * n;
   const T* gb = g + b * n;
   float szz = 0.0f, sgz = 0.0f;
-  for (int64_t i = lane; i < n; i += 64) {
+#pragma unroll 8
+  for (int64_t i = lane; i < n; i += TPS) {
     const float zv = Store<T>::ld(zb + i), gv = Store<T>::ld(gb + i);
     szz = fmaf(zv, zv, szz);
     sgz = fmaf(gv, zv, sgz);
   }
-  szz = wave_sum(szz);
-  sgz = wave_sum(sgz);
+  szz = sample_sum<TPS>(szz, sm);
+  sgz = sample_sum<TPS>(sgz, sm);
   const float ms = szz / (float)n;
   float inv_r = 0.0f, coef = 0.0f;
   if (ms > 0.0f) {
     inv_r = 1.0f / sqrtf(ms);
     coef = sgz / (float)n * inv_r * inv_r * inv_r;
   }
-  for (int64_t i = lane; i < n; i += 64) {
+#pragma unroll 8
+  for (int64_t i = lane; i < n; i += TPS) {
     const float zv = Store<T>::ld(zb + i), gv = Store<T>::ld(gb + i);
     Store<T>::st(dz + b * n + i, gv * inv_r - zv * coef);
   }
@@ -255,31 +267,38 @@ inline int grid_for(int64_t items, int cap) {
 
 }  // namespace
 
+// small batches of long vectors get a whole workgroup per sample
+static bool block_per_sample(int64_t batch, int64_t n) { return batch < 1024 && n >= 1024; }
+
 int launch_pnorm_awgn(const void* z, void* y, int64_t batch, int c, int hw, int dtype, int do_pnorm, int do_awgn,
                       float sigma, uint64_t seed, uint64_t first_sample, hipStream_t s) {
-  const int64_t blocks = (batch + NT / 64 - 1) / (NT / 64);
-  if (blocks > 0x7FFFFFFF) return fail(AE_EINVAL, "pnorm_awgn: batch too large");
   // a flat vector is a tensor with hw == 1 (or c == 1: then (c,h,w) order is storage order too)
   int C = c, HW = hw;
   if (C == 1) { C = HW; HW = 1; }
   const bool flat = HW == 1 && (C % 4 == 0);
-#define LAUNCH(T, F)                                                                                              \
-  hipLaunchKernelGGL((k_pnorm_awgn<T, F>), dim3((unsigned)blocks), dim3(NT), 0, s, (const T*)z, (T*)y, batch, C, HW, \
-                     do_pnorm, do_awgn, sigma, seed, first_sample)
-  if (dtype == AE_BF16) { if (flat) LAUNCH(bf16_t, true); else LAUNCH(bf16_t, false); }
-  else { if (flat) LAUNCH(float, true); else LAUNCH(float, false); }
+  const bool wide = block_per_sample(batch, (int64_t)C * HW);
+  const int64_t blocks = wide ? batch : (batch + NT / 64 - 1) / (NT / 64);
+  if (blocks > 0x7FFFFFFF) return fail(AE_EINVAL, "pnorm_awgn: batch too large");
+#define LAUNCH(T, F, TPSV)                                                                                          \
+  hipLaunchKernelGGL((k_pnorm_awgn<T, F, TPSV>), dim3((unsigned)blocks), dim3(NT), 0, s, (const T*)z, (T*)y, batch, C, \
+                     HW, do_pnorm, do_awgn, sigma, seed, first_sample)
+#define LAUNCH_F(T, F) do { if (wide) LAUNCH(T, F, 256); else LAUNCH(T, F, 64); } while (0)
+  if (dtype == AE_BF16) { if (flat) LAUNCH_F(bf16_t, true); else LAUNCH_F(bf16_t, false); }
+  else { if (flat) LAUNCH_F(float, true); else LAUNCH_F(float, false); }
+#undef LAUNCH_F
 #undef LAUNCH
   return launch_status("pnorm_awgn");
 }
 
 int launch_pnorm_bwd(const void* z, const void* g, void* dz, int64_t batch, int64_t n, int dtype, hipStream_t s) {
-  const int64_t blocks = (batch + NT / 64 - 1) / (NT / 64);
-  if (dtype == AE_BF16)
-    hipLaunchKernelGGL((k_pnorm_bwd<bf16_t>), dim3((unsigned)blocks), dim3(NT), 0, s, (const bf16_t*)z, (const bf16_t*)g,
-                       (bf16_t*)dz, batch, n);
-  else
-    hipLaunchKernelGGL((k_pnorm_bwd<float>), dim3((unsigned)blocks), dim3(NT), 0, s, (const float*)z, (const float*)g,
-                       (float*)dz, batch, n);
+  const bool wide = block_per_sample(batch, n);
+  const int64_t blocks = wide ? batch : (batch + NT / 64 - 1) / (NT / 64);
+#define LAUNCH(T, TPSV)                                                                                             \
+  hipLaunchKernelGGL((k_pnorm_bwd<T, TPSV>), dim3((unsigned)blocks), dim3(NT), 0, s, (const T*)z, (const T*)g, (T*)dz, \
+                     batch, n)
+  if (dtype == AE_BF16) { if (wide) LAUNCH(bf16_t, 256); else LAUNCH(bf16_t, 64); }
+  else { if (wide) LAUNCH(float, 256); else LAUNCH(float, 64); }
+#undef LAUNCH
   return launch_status("pnorm_bwd");
 }
 

@@ -256,7 +256,8 @@ int build_plan(const char* spec, int batch, int dtype, int bn_mode, Plan* plan) 
       plan->max_full_elems = std::max(plan->max_full_elems, rows * st.cin);
       int64_t wel = (int64_t)st.cout * st.cin * st.k * st.k;
       // thin layers keep their weights repacked as MFMA operand rows of the wide side
-      st.off_wpack = take(std::max(wel * es, st.thin == 1 ? thin_wfrag_bytes(st.cout) : (int64_t)0));
+      st.off_wpack = take(std::max(wel * es, st.thin == 1 ? thin_wfrag_bytes(st.cout)
+                                             : st.thin == 2 ? thin_out_wz_bytes(st.cout, st.cin) : (int64_t)0));
       st.off_wpack_d = take(std::max(wel * es, st.thin == 2 ? thin_wfrag_bytes(st.cin) : (int64_t)0));
       if (st.has_bn) st.off_bn = take(6 * (int64_t)st.cout * 4);
       int64_t blocks = std::max<int64_t>((rows + 127) / 128, reduce_blocks(rows));  // finest partial-sum granularity
@@ -281,7 +282,9 @@ int build_plan(const char* spec, int batch, int dtype, int bn_mode, Plan* plan) 
       }
       else if (wgrad_mfma_supported(wa))
         plan->max_wgrad_floats = std::max(plan->max_wgrad_floats, wgrad_mfma_workspace_floats(st.cout, st.cin, st.k, rows));
-      if (st.thin == 2) plan->max_partial_floats = std::max(plan->max_partial_floats, B * 2 * (int64_t)st.cout);
+      if (st.thin == 2)
+        plan->max_partial_floats = std::max(plan->max_partial_floats,
+                                            B * plane_sums_split((int64_t)st.hc * st.wc) * 2 * (int64_t)st.cout);
     }
   }
   plan->off_grad_a = take(plan->max_act_elems * es);      // gradient ping-pong
