@@ -145,6 +145,7 @@ __global__ void k_bn_finalize(const float* __restrict__ partial, int nblocks, do
     var = (double)stored_mean_var[C + c];
   } else {
     double s1 = 0.0, s2 = 0.0;
+#pragma unroll 8
     for (int b = threadIdx.x; b < nblocks; b += NT) {
       s1 += (double)partial[((int64_t)b * 2) * C + c];
       s2 += (double)partial[((int64_t)b * 2 + 1) * C + c];
@@ -183,45 +184,67 @@ __device__ __forceinline__ void load_f32(const float* p, float (&v)[VEC]) {
   for (int j = 0; j < VEC; ++j) v[j] = p[j];
 }
 
+// Thread layout shared by the second-pass kernels: a workgroup owns `rpb` consecutive output
+// pixels (rows); thread (cg, rl) keeps its channel group's batch-norm vectors in registers and
+// walks over rows rl, rl + nrl, ...
+struct RowWalk {
+  int tpr, nrl, cg, rl;
+  bool active;
+  __device__ __forceinline__ RowWalk(int groups) {
+    tpr = groups < NT ? groups : NT;
+    nrl = NT / tpr;
+    cg = threadIdx.x % tpr;
+    rl = threadIdx.x / tpr;
+    active = rl < nrl;
+  }
+};
+
 // out = pool?( act( scale*raw + shift ) ); bn_vec == null means scale 1, shift 0
 template <typename T, int VEC>
 __global__ void k_post_forward(const T* __restrict__ raw, const float* __restrict__ bn_vec, T* __restrict__ out,
-                               int64_t n, int H, int W, int C, int act, int pool) {
+                               int64_t n, int H, int W, int C, int act, int pool, int rpb) {
   const int groups = C / VEC;
   const int Ho = H >> pool, Wo = W >> pool;
-  const int64_t total = n * Ho * Wo * groups;
-  for (int64_t it = (int64_t)blockIdx.x * NT + threadIdx.x; it < total; it += (int64_t)gridDim.x * NT) {
-    const unsigned iu = (unsigned)it;             // total < 2^31 (checked by the launcher): 32-bit divisions
-    const int c = (int)(iu % (unsigned)groups) * VEC;
-    unsigned p = iu / (unsigned)groups;
-    const int wo = (int)(p % (unsigned)Wo); p /= (unsigned)Wo;
-    const int ho = (int)(p % (unsigned)Ho);
-    const int64_t b = p / (unsigned)Ho;
+  const int64_t rows = n * Ho * Wo;
+  const RowWalk t(groups);
+  const int64_t r0 = (int64_t)blockIdx.x * rpb;
+  const int64_t r1 = r0 + rpb < rows ? r0 + rpb : rows;
+  for (int cbase = 0; cbase < C; cbase += t.tpr * VEC) {
+    const int c = cbase + t.cg * VEC;
+    if (!t.active || c >= C) continue;
     float sc[VEC], sh[VEC];
     if (bn_vec) { load_f32<VEC>(bn_vec + c, sc); load_f32<VEC>(bn_vec + C + c, sh); }
     else {
 #pragma unroll
       for (int j = 0; j < VEC; ++j) { sc[j] = 1.0f; sh[j] = 0.0f; }
     }
-    float res[VEC];
-    if (pool) {
+#pragma unroll 2
+    for (int64_t r = r0 + t.rl; r < r1; r += t.nrl) {
+      const unsigned ru = (unsigned)r;              // rows < 2^31 (checked by the launcher): 32-bit divisions
+      const int wo = (int)(ru % (unsigned)Wo);
+      const unsigned q = ru / (unsigned)Wo;
+      const int ho = (int)(q % (unsigned)Ho);
+      const int64_t b = q / (unsigned)Ho;
+      float res[VEC];
+      if (pool) {
+        float v[4][VEC];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
+        for (int k = 0; k < 4; ++k) load_vec<T, VEC>(raw + ((b * H + 2 * ho + (k >> 1)) * W + 2 * wo + (k & 1)) * C + c, v[k]);
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+#pragma unroll
+          for (int j = 0; j < VEC; ++j) {
+            const float a = apply_act(fmaf(sc[j], v[k][j], sh[j]), act);
+            res[j] = (k == 0 || a > res[j]) ? a : res[j];
+          }
+      } else {
         float v[VEC];
-        load_vec<T, VEC>(raw + ((b * H + 2 * ho + (q >> 1)) * W + 2 * wo + (q & 1)) * C + c, v);
+        load_vec<T, VEC>(raw + r * C + c, v);
 #pragma unroll
-        for (int j = 0; j < VEC; ++j) {
-          float a = apply_act(fmaf(sc[j], v[j], sh[j]), act);
-          res[j] = (q == 0 || a > res[j]) ? a : res[j];
-        }
+        for (int j = 0; j < VEC; ++j) res[j] = apply_act(fmaf(sc[j], v[j], sh[j]), act);
       }
-    } else {
-      float v[VEC];
-      load_vec<T, VEC>(raw + ((b * H + ho) * W + wo) * C + c, v);
-#pragma unroll
-      for (int j = 0; j < VEC; ++j) res[j] = apply_act(fmaf(sc[j], v[j], sh[j]), act);
+      store_vec<T, VEC>(out + r * C + c, res);
     }
-    store_vec<T, VEC>(out + ((b * Ho + ho) * Wo + wo) * C + c, res);
   }
 }
 
@@ -229,6 +252,18 @@ __device__ __forceinline__ float act_grad(float pre, float a, int act) {
   if (act == 1) return pre > 0.0f ? 1.0f : 0.0f;
   if (act == 2) return a * (1.0f - a);
   return 1.0f;
+}
+
+template <int VEC>
+__device__ __forceinline__ void load_bn4(const float* __restrict__ bn_vec, int C, int c, float (&sc)[VEC], float (&sh)[VEC],
+                                         float (&mu)[VEC], float (&is)[VEC]) {
+  if (bn_vec) {
+    load_f32<VEC>(bn_vec + c, sc); load_f32<VEC>(bn_vec + C + c, sh);
+    load_f32<VEC>(bn_vec + 2 * C + c, mu); load_f32<VEC>(bn_vec + 3 * C + c, is);
+  } else {
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) { sc[j] = 1.0f; sh[j] = 0.0f; mu[j] = 0.0f; is[j] = 1.0f; }
+  }
 }
 
 // Backward of the second pass, shared by the reduction and the apply kernels: for
@@ -240,32 +275,27 @@ struct PostBwdWindow {
   static constexpr int NQ = POOL ? 4 : 1;
   float dy[NQ][VEC];
   float xh[NQ][VEC];
-  __device__ __forceinline__ void compute(const T* __restrict__ raw, const T* __restrict__ dout,
-                                          const float* __restrict__ bn_vec, int64_t b, int ho, int wo, int H, int W,
-                                          int C, int c, int act) {
+  __device__ __forceinline__ void compute(const T* __restrict__ raw, const T* __restrict__ dout, const float (&sc)[VEC],
+                                          const float (&sh)[VEC], const float (&mu)[VEC], const float (&is)[VEC],
+                                          int64_t b, int ho, int wo, int H, int W, int C, int c, int act) {
     const int Ho = POOL ? H >> 1 : H, Wo = POOL ? W >> 1 : W;
-    float sc[VEC], sh[VEC], mu[VEC], is[VEC];
-    if (bn_vec) {
-      load_f32<VEC>(bn_vec + c, sc); load_f32<VEC>(bn_vec + C + c, sh);
-      load_f32<VEC>(bn_vec + 2 * C + c, mu); load_f32<VEC>(bn_vec + 3 * C + c, is);
-    } else {
-#pragma unroll
-      for (int j = 0; j < VEC; ++j) { sc[j] = 1.0f; sh[j] = 0.0f; mu[j] = 0.0f; is[j] = 1.0f; }
-    }
     float g[VEC];
     load_vec<T, VEC>(dout + ((b * Ho + ho) * Wo + wo) * C + c, g);
     float best[VEC], dbest[VEC];
     int arg[VEC];
+    float v[NQ][VEC];
 #pragma unroll
     for (int q = 0; q < NQ; ++q) {
-      float v[VEC];
       const int hh = POOL ? 2 * ho + (q >> 1) : ho, ww = POOL ? 2 * wo + (q & 1) : wo;
-      load_vec<T, VEC>(raw + ((b * H + hh) * W + ww) * C + c, v);
+      load_vec<T, VEC>(raw + ((b * H + hh) * W + ww) * C + c, v[q]);
+    }
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
 #pragma unroll
       for (int j = 0; j < VEC; ++j) {
-        const float pre = fmaf(sc[j], v[j], sh[j]);
+        const float pre = fmaf(sc[j], v[q][j], sh[j]);
         const float a = apply_act(pre, act);
-        xh[q][j] = (v[j] - mu[j]) * is[j];
+        xh[q][j] = (v[q][j] - mu[j]) * is[j];
         if (q == 0 || a > best[j]) { best[j] = a; arg[j] = q; dbest[j] = act_grad(pre, a, act); }
       }
     }
@@ -298,13 +328,15 @@ __global__ void k_post_bwd_reduce(const T* __restrict__ raw, const T* __restrict
     for (int v = 0; v < VEC; ++v) acc[0][v] = acc[1][v] = 0.0f;
     const int c = cbase + cg * VEC;
     if (active && c < C) {
+      float sc[VEC], sh[VEC], mu[VEC], is[VEC];
+      load_bn4<VEC>(bn_vec, C, c, sc, sh, mu, is);
       for (int64_t r = r0 + rl; r < r1; r += nrl) {
         const unsigned ru = (unsigned)r;              // rows < 2^31 (checked by the launcher)
         const int wo = (int)(ru % (unsigned)Wo);
         const int ho = (int)((ru / (unsigned)Wo) % (unsigned)Ho);
         const int64_t b = ru / ((unsigned)Wo * (unsigned)Ho);
         PostBwdWindow<T, VEC, POOL> win;
-        win.compute(raw, dout, bn_vec, b, ho, wo, H, W, C, c, act);
+        win.compute(raw, dout, sc, sh, mu, is, b, ho, wo, H, W, C, c, act);
 #pragma unroll
         for (int q = 0; q < PostBwdWindow<T, VEC, POOL>::NQ; ++q)
 #pragma unroll
@@ -322,6 +354,7 @@ __global__ void k_bn_bwd_finalize(const float* __restrict__ partial, int nblocks
   __shared__ double sm[NT / 64 + 1];
   const int c = blockIdx.x;
   double s1 = 0.0, s2 = 0.0;
+#pragma unroll 8
   for (int b = threadIdx.x; b < nblocks; b += NT) {
     s1 += (double)partial[((int64_t)b * 2) * C + c];
     s2 += (double)partial[((int64_t)b * 2 + 1) * C + c];
@@ -345,29 +378,36 @@ __global__ void k_bn_bwd_finalize(const float* __restrict__ partial, int nblocks
 template <typename T, int VEC, bool POOL>
 __global__ void k_post_bwd_apply(const T* __restrict__ raw, const T* __restrict__ dout,
                                  const float* __restrict__ bn_vec, T* __restrict__ draw, int64_t n, int H, int W,
-                                 int C, int act, int has_bn) {
+                                 int C, int act, int has_bn, int rpb) {
   const int groups = C / VEC;
   const int Ho = POOL ? H >> 1 : H, Wo = POOL ? W >> 1 : W;
-  const int64_t total = n * Ho * Wo * groups;
-  for (int64_t it = (int64_t)blockIdx.x * NT + threadIdx.x; it < total; it += (int64_t)gridDim.x * NT) {
-    const unsigned iu = (unsigned)it;             // total < 2^31 (checked by the launcher): 32-bit divisions
-    const int c = (int)(iu % (unsigned)groups) * VEC;
-    unsigned p = iu / (unsigned)groups;
-    const int wo = (int)(p % (unsigned)Wo); p /= (unsigned)Wo;
-    const int ho = (int)(p % (unsigned)Ho);
-    const int64_t b = p / (unsigned)Ho;
-    PostBwdWindow<T, VEC, POOL> win;
-    win.compute(raw, dout, bn_vec, b, ho, wo, H, W, C, c, act);
-    float sc[VEC], c1[VEC], c2[VEC];
-    if (has_bn) { load_f32<VEC>(bn_vec + c, sc); load_f32<VEC>(bn_vec + 4 * C + c, c1); load_f32<VEC>(bn_vec + 5 * C + c, c2); }
+  const int64_t rows = n * Ho * Wo;
+  const RowWalk t(groups);
+  const int64_t r0 = (int64_t)blockIdx.x * rpb;
+  const int64_t r1 = r0 + rpb < rows ? r0 + rpb : rows;
+  for (int cbase = 0; cbase < C; cbase += t.tpr * VEC) {
+    const int c = cbase + t.cg * VEC;
+    if (!t.active || c >= C) continue;
+    float sc[VEC], sh[VEC], mu[VEC], is[VEC], c1[VEC], c2[VEC];
+    load_bn4<VEC>(bn_vec, C, c, sc, sh, mu, is);
+    if (has_bn) { load_f32<VEC>(bn_vec + 4 * C + c, c1); load_f32<VEC>(bn_vec + 5 * C + c, c2); }
+    for (int64_t r = r0 + t.rl; r < r1; r += t.nrl) {
+      const unsigned ru = (unsigned)r;              // rows < 2^31 (checked by the launcher): 32-bit divisions
+      const int wo = (int)(ru % (unsigned)Wo);
+      const unsigned q_ = ru / (unsigned)Wo;
+      const int ho = (int)(q_ % (unsigned)Ho);
+      const int64_t b = q_ / (unsigned)Ho;
+      PostBwdWindow<T, VEC, POOL> win;
+      win.compute(raw, dout, sc, sh, mu, is, b, ho, wo, H, W, C, c, act);
 #pragma unroll
-    for (int q = 0; q < PostBwdWindow<T, VEC, POOL>::NQ; ++q) {
-      float o[VEC];
+      for (int q = 0; q < PostBwdWindow<T, VEC, POOL>::NQ; ++q) {
+        float o[VEC];
 #pragma unroll
-      for (int j = 0; j < VEC; ++j)
-        o[j] = has_bn ? sc[j] * (win.dy[q][j] - c1[j] - win.xh[q][j] * c2[j]) : win.dy[q][j];
-      const int hh = POOL ? 2 * ho + (q >> 1) : ho, ww = POOL ? 2 * wo + (q & 1) : wo;
-      store_vec<T, VEC>(draw + ((b * H + hh) * W + ww) * C + c, o);
+        for (int j = 0; j < VEC; ++j)
+          o[j] = has_bn ? sc[j] * (win.dy[q][j] - c1[j] - win.xh[q][j] * c2[j]) : win.dy[q][j];
+        const int hh = POOL ? 2 * ho + (q >> 1) : ho, ww = POOL ? 2 * wo + (q & 1) : wo;
+        store_vec<T, VEC>(draw + ((b * H + hh) * W + ww) * C + c, o);
+      }
     }
   }
 }
@@ -426,6 +466,7 @@ __global__ void k_colsum_finalize(const float* __restrict__ partial, int nblocks
   __shared__ double sm[NT / 64 + 1];
   const int c = blockIdx.x;
   double s1 = 0.0;
+#pragma unroll 8
   for (int b = threadIdx.x; b < nblocks; b += NT) s1 += (double)partial[((int64_t)b * 2) * C + c];
   s1 = block_sum<NT>(s1, sm);
   if (threadIdx.x == 0) out[c] = (float)s1;
@@ -499,6 +540,16 @@ __global__ void k_mse(const T* __restrict__ y, const T* __restrict__ t, int64_t 
     else { typedef float T; __VA_ARGS__; }                      \
   } while (0)
 
+// rows per workgroup of the row-walking kernels: up to 8 rows per thread, fewer when that
+// would leave the machine with fewer than about 2048 workgroups
+static int walk_rows_per_block(int64_t rows, int groups) {
+  const int tpr = groups < NT ? groups : NT;
+  const int nrl = NT / tpr;
+  int it = 8;
+  while (it > 1 && rows / ((int64_t)nrl * it) < 2048) it >>= 1;
+  return nrl * it;
+}
+
 #define DISPATCH_T_VEC(dtype, C, ...)                                                       \
   do {                                                                                      \
     if ((dtype) == AE_BF16) {                                                               \
@@ -546,10 +597,11 @@ int launch_bn_finalize(const float* partial, int nblocks, int64_t rows, int c, c
 int launch_post_forward(const void* raw, const float* bn_vec, void* out, int64_t n, int h, int w, int c, int act,
                         int pool, int dtype, hipStream_t s) {
   DISPATCH_T_VEC(dtype, c, {
-    int64_t items = n * (h >> pool) * (w >> pool) * (c / VEC);
-    if (items >= 0x7FFFFFFF) return fail(AE_EINVAL, "post_forward: tensor too large");
-    hipLaunchKernelGGL((k_post_forward<T, VEC>), dim3(grid_for(items)), dim3(NT), 0, s, (const T*)raw, bn_vec, (T*)out,
-                       n, h, w, c, act, pool);
+    const int64_t rows = n * (h >> pool) * (w >> pool);
+    if (rows * (c / VEC) >= 0x7FFFFFFF) return fail(AE_EINVAL, "post_forward: tensor too large");
+    const int rpb = walk_rows_per_block(rows, c / VEC);
+    hipLaunchKernelGGL((k_post_forward<T, VEC>), dim3((unsigned)((rows + rpb - 1) / rpb)), dim3(NT), 0, s, (const T*)raw,
+                       bn_vec, (T*)out, n, h, w, c, act, pool, rpb);
   });
   return launch_status("post_forward");
 }
@@ -581,14 +633,16 @@ int launch_bn_bwd_finalize(const float* partial, int nblocks, int64_t rows, int 
 int launch_post_bwd_apply(const void* raw, const void* dout, const float* bn_vec, void* draw, int64_t n, int h, int w,
                           int c, int act, int pool, int has_bn, int dtype, hipStream_t s) {
   DISPATCH_T_VEC(dtype, c, {
-    int64_t items = n * (h >> pool) * (w >> pool) * (c / VEC);
-    if (items >= 0x7FFFFFFF) return fail(AE_EINVAL, "post_bwd_apply: tensor too large");
+    const int64_t rows = n * (h >> pool) * (w >> pool);
+    if (rows * (c / VEC) >= 0x7FFFFFFF) return fail(AE_EINVAL, "post_bwd_apply: tensor too large");
+    const int rpb = walk_rows_per_block(rows, c / VEC);
+    const dim3 grid((unsigned)((rows + rpb - 1) / rpb));
     if (pool)
-      hipLaunchKernelGGL((k_post_bwd_apply<T, VEC, true>), dim3(grid_for(items)), dim3(NT), 0, s, (const T*)raw,
-                         (const T*)dout, bn_vec, (T*)draw, n, h, w, c, act, has_bn);
+      hipLaunchKernelGGL((k_post_bwd_apply<T, VEC, true>), grid, dim3(NT), 0, s, (const T*)raw, (const T*)dout, bn_vec,
+                         (T*)draw, n, h, w, c, act, has_bn, rpb);
     else
-      hipLaunchKernelGGL((k_post_bwd_apply<T, VEC, false>), dim3(grid_for(items)), dim3(NT), 0, s, (const T*)raw,
-                         (const T*)dout, bn_vec, (T*)draw, n, h, w, c, act, has_bn);
+      hipLaunchKernelGGL((k_post_bwd_apply<T, VEC, false>), grid, dim3(NT), 0, s, (const T*)raw, (const T*)dout, bn_vec,
+                         (T*)draw, n, h, w, c, act, has_bn, rpb);
   });
   return launch_status("post_bwd_apply");
 }
