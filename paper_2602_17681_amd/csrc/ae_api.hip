@@ -198,9 +198,9 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
   if (st.has_bn || st.pool) {
     if (st.has_bn) {
       const int64_t prow = (int64_t)P.batch * st.hout * st.wout;
-      TIMED(si, "bwd.bn_reduce", 0.0, (raw_el + out_el) * es,
-            launch_post_bwd_reduce(st.raw, g, st.bn_vec, P.batch, st.hc, st.wc, st.cout, st.act, st.pool, P.dtype,
-                                   m->partial, s));
+      TIMED(si, "bwd.bn_reduce", 0.0, (st.act == ACT_RELU ? 2.0 * out_el : raw_el + out_el) * es,
+            launch_post_bwd_reduce(st.raw, g, st.out, st.bn_vec, P.batch, st.hc, st.wc, st.cout, st.act, st.pool,
+                                   P.dtype, m->partial, s));
       TIMED(si, "bwd.bn_finalize", 0.0, 0.0,
             launch_bn_bwd_finalize(m->partial, nblocks_for(prow), rows, st.cout, grads + st.b_off, st.bn_vec,
                                    grads + st.bn_off, P.bn_mode == 0, s));

@@ -306,9 +306,14 @@ struct PostBwdWindow {
   }
 };
 
-// partial[b][0][c] = sum dy, partial[b][1][c] = sum dy*xhat over the block's output pixels
+// partial[b][0][c] = sum dy, partial[b][1][c] = sum dy*xhat over the block's output pixels.
+// With ReLU (out_act given) the sums need no pass over the conv output: the gradient reaches only
+// the position that produced the stored activation a = max(pre, 0) > 0 of each (pooled) output,
+// where pre = a, and xhat follows from pre = scale*raw + shift: xhat = a*p1 + p0 with
+// p1 = invstd/scale, p0 = -(shift/scale + mean)*invstd.  Channels with scale == 0 take the
+// general path.
 template <typename T, int VEC, bool POOL>
-__global__ void k_post_bwd_reduce(const T* __restrict__ raw, const T* __restrict__ dout,
+__global__ void k_post_bwd_reduce(const T* __restrict__ raw, const T* __restrict__ dout, const T* __restrict__ out_act,
                                   const float* __restrict__ bn_vec, int64_t n, int H, int W, int C, int act,
                                   int rpb, float* __restrict__ partial) {
   __shared__ float smem[NT * 2 * VEC];
@@ -330,17 +335,42 @@ __global__ void k_post_bwd_reduce(const T* __restrict__ raw, const T* __restrict
     if (active && c < C) {
       float sc[VEC], sh[VEC], mu[VEC], is[VEC];
       load_bn4<VEC>(bn_vec, C, c, sc, sh, mu, is);
-      for (int64_t r = r0 + rl; r < r1; r += nrl) {
-        const unsigned ru = (unsigned)r;              // rows < 2^31 (checked by the launcher)
-        const int wo = (int)(ru % (unsigned)Wo);
-        const int ho = (int)((ru / (unsigned)Wo) % (unsigned)Ho);
-        const int64_t b = ru / ((unsigned)Wo * (unsigned)Ho);
-        PostBwdWindow<T, VEC, POOL> win;
-        win.compute(raw, dout, sc, sh, mu, is, b, ho, wo, H, W, C, c, act);
+      bool from_act = out_act != nullptr;
 #pragma unroll
-        for (int q = 0; q < PostBwdWindow<T, VEC, POOL>::NQ; ++q)
+      for (int j = 0; j < VEC; ++j) from_act = from_act && sc[j] != 0.0f;
+      if (from_act) {
+        float p1[VEC], p0[VEC];
 #pragma unroll
-          for (int j = 0; j < VEC; ++j) { acc[0][j] += win.dy[q][j]; acc[1][j] = fmaf(win.dy[q][j], win.xh[q][j], acc[1][j]); }
+        for (int j = 0; j < VEC; ++j) {
+          const float inv = 1.0f / sc[j];
+          p1[j] = is[j] * inv;
+          p0[j] = -(sh[j] * inv + mu[j]) * is[j];
+        }
+#pragma unroll 4
+        for (int64_t r = r0 + rl; r < r1; r += nrl) {
+          float a[VEC], g[VEC];
+          load_vec<T, VEC>(out_act + r * C + c, a);
+          load_vec<T, VEC>(dout + r * C + c, g);
+#pragma unroll
+          for (int j = 0; j < VEC; ++j) {
+            const float dyv = a[j] > 0.0f ? g[j] : 0.0f;
+            acc[0][j] += dyv;
+            acc[1][j] = fmaf(dyv, fmaf(a[j], p1[j], p0[j]), acc[1][j]);
+          }
+        }
+      } else {
+        for (int64_t r = r0 + rl; r < r1; r += nrl) {
+          const unsigned ru = (unsigned)r;              // rows < 2^31 (checked by the launcher)
+          const int wo = (int)(ru % (unsigned)Wo);
+          const int ho = (int)((ru / (unsigned)Wo) % (unsigned)Ho);
+          const int64_t b = ru / ((unsigned)Wo * (unsigned)Ho);
+          PostBwdWindow<T, VEC, POOL> win;
+          win.compute(raw, dout, sc, sh, mu, is, b, ho, wo, H, W, C, c, act);
+#pragma unroll
+          for (int q = 0; q < PostBwdWindow<T, VEC, POOL>::NQ; ++q)
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) { acc[0][j] += win.dy[q][j]; acc[1][j] = fmaf(win.dy[q][j], win.xh[q][j], acc[1][j]); }
+        }
       }
     }
     block_col_combine<VEC, 2>(acc, cg, rl, nrl, tpr, cbase, C, pb, smem, active);
@@ -606,8 +636,10 @@ int launch_post_forward(const void* raw, const float* bn_vec, void* out, int64_t
   return launch_status("post_forward");
 }
 
-int launch_post_bwd_reduce(const void* raw, const void* dout, const float* bn_vec, int64_t n, int h, int w, int c,
-                           int act, int pool, int dtype, float* partial, hipStream_t s) {
+// out_act: the step's stored output (after activation and pooling); used when act is ReLU
+int launch_post_bwd_reduce(const void* raw, const void* dout, const void* out_act, const float* bn_vec, int64_t n, int h,
+                           int w, int c, int act, int pool, int dtype, float* partial, hipStream_t s) {
+  if (act != ACT_RELU || !bn_vec) out_act = nullptr;
   int64_t rows = n * (h >> pool) * (w >> pool);
   if (rows >= 0x7FFFFFFF) return fail(AE_EINVAL, "post_bwd_reduce: tensor too large");
   const int rpb = reduce_rows_per_block(rows);
@@ -615,10 +647,10 @@ int launch_post_bwd_reduce(const void* raw, const void* dout, const float* bn_ve
   DISPATCH_T_VEC(dtype, c, {
     if (pool)
       hipLaunchKernelGGL((k_post_bwd_reduce<T, VEC, true>), dim3(nblocks), dim3(NT), 0, s, (const T*)raw,
-                         (const T*)dout, bn_vec, n, h, w, c, act, rpb, partial);
+                         (const T*)dout, (const T*)out_act, bn_vec, n, h, w, c, act, rpb, partial);
     else
       hipLaunchKernelGGL((k_post_bwd_reduce<T, VEC, false>), dim3(nblocks), dim3(NT), 0, s, (const T*)raw,
-                         (const T*)dout, bn_vec, n, h, w, c, act, rpb, partial);
+                         (const T*)dout, (const T*)out_act, bn_vec, n, h, w, c, act, rpb, partial);
   });
   return launch_status("post_bwd_reduce");
 }

@@ -166,8 +166,8 @@ int launch_bn_finalize(const float* partial, int nblocks, int64_t rows, int c, c
                        const float* stored_mean_var, float* bn_vec, hipStream_t s);
 int launch_post_forward(const void* raw, const float* bn_vec, void* out, int64_t n, int h, int w, int c, int act,
                         int pool, int dtype, hipStream_t s);
-int launch_post_bwd_reduce(const void* raw, const void* dout, const float* bn_vec, int64_t n, int h, int w, int c,
-                           int act, int pool, int dtype, float* partial, hipStream_t s);
+int launch_post_bwd_reduce(const void* raw, const void* dout, const void* out_act, const float* bn_vec, int64_t n, int h,
+                           int w, int c, int act, int pool, int dtype, float* partial, hipStream_t s);
 int launch_bn_bwd_finalize(const float* partial, int nblocks, int64_t rows, int c, float* dbias, float* bn_vec,
                            float* dgamma_dbeta, int batch_stats, hipStream_t s);
 int launch_act_bwd_colsum(const void* out, const float* out_f32, const void* dout, void* draw, int64_t rows, int c,
