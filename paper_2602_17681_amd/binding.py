@@ -122,7 +122,7 @@ class Model:
         self.in_shape, self.out_shape, self.latent_n = tuple(ic), tuple(oc), lat.value
 
     def close(self):
-        if getattr(self, "_h", None) and self._h.value:
+        if getattr(self, "_h", None) and self._h.value and lib is not None:   # lib is None at interpreter shutdown
             lib.model_destroy(self._h)
             self._h = C.c_void_p()
 

@@ -38,6 +38,7 @@ struct ae_model {
   float* wgrad_ws = nullptr;
   uint64_t first_sample = 0;
   bool have_forward = false;
+  bool packed_in_batch = false;     // the current pass repacked all its weights with one launch
 };
 
 using namespace ae;
@@ -97,6 +98,35 @@ int nblocks_for(int64_t rows) { return reduce_blocks(rows); }
 // input tensor of step i: the previous step's saved output, or the caller's x
 const void* step_input(const ae_model* m, size_t i, const void* x) { return i == 0 ? x : m->plan.steps[i - 1].out; }
 
+// forward: does this conv step read repacked weights?
+bool needs_fwd_pack(const Plan& P, const Step& st) {
+  return st.kind == ST_CONV && st.thin == 0 && !(st.k == 1 && P.dtype == AE_F32 && !st.mfma);
+}
+bool needs_dgrad_pack(const Step& st) { return st.kind == ST_CONV && st.thin == 0 && st.needs_dx; }
+
+// Repack the weights of every layer of a pass with one launch (more layers than a batch
+// holds: the per-layer launches remain).
+int pack_all(ae_model* m, const float* params, bool dgrad, hipStream_t s) {
+  const Plan& P = m->plan;
+  PackBatch pb;
+  pb.n = 0;
+  double bytes = 0.0;
+  m->packed_in_batch = false;
+  for (const Step& st : P.steps) {
+    const bool want = dgrad ? needs_dgrad_pack(st) : needs_fwd_pack(P, st);
+    if (!want) continue;
+    if (pb.n == kMaxPackJobs) return AE_OK;      // too many layers: fall back to per-layer packing
+    PackJob& j = pb.job[pb.n++];
+    j.w = params + st.w_off; j.wp = dgrad ? st.wpack_d : st.wpack;
+    j.cout = st.cout; j.cin = st.cin; j.k = st.k; j.dgrad = dgrad ? 1 : 0; j.first_block = 0;
+    bytes += (double)st.cout * st.cin * st.k * st.k * (4.0 + (double)dtype_size(P.dtype));
+  }
+  if (pb.n == 0) return AE_OK;
+  TIMED(0, dgrad ? "bwd.pack_weights_all" : "fwd.pack_weights_all", 0.0, bytes, launch_pack_weights_batch(pb, P.dtype, s));
+  m->packed_in_batch = true;
+  return AE_OK;
+}
+
 int forward_conv(ae_model* m, int si, Step& st, const float* params, const void* in, hipStream_t s) {
   const Plan& P = m->plan;
   const double es = (double)dtype_size(P.dtype);
@@ -121,8 +151,9 @@ int forward_conv(ae_model* m, int si, Step& st, const float* params, const void*
   } else if (st.k == 1 && P.dtype == AE_F32 && !st.mfma) {
     w = params + st.w_off;  // [C_out][C_in] is already the packed order (the MFMA loader wants a 16-byte aligned copy)
   } else {
-    TIMED(si, "fwd.pack_weights", 0.0, wel * (4.0 + es),
-          launch_pack_weights(params + st.w_off, st.wpack, st.cout, st.cin, st.k, P.dtype, false, s));
+    if (!m->packed_in_batch)
+      TIMED(si, "fwd.pack_weights", 0.0, wel * (4.0 + es),
+            launch_pack_weights(params + st.w_off, st.wpack, st.cout, st.cin, st.k, P.dtype, false, s));
     w = st.wpack;
   }
   const bool second_pass = st.has_bn || st.pool;
@@ -283,8 +314,9 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
   }
   // input gradient: convolution of dr with the flipped, transposed weights at conv resolution
   if (st.needs_dx) {
-    TIMED(si, "bwd.pack_weights", 0.0, wel * (4.0 + es),
-          launch_pack_weights(params + st.w_off, st.wpack_d, st.cout, st.cin, st.k, P.dtype, true, s));
+    if (!m->packed_in_batch)
+      TIMED(si, "bwd.pack_weights", 0.0, wel * (4.0 + es),
+            launch_pack_weights(params + st.w_off, st.wpack_d, st.cout, st.cin, st.k, P.dtype, true, s));
     ConvArgs a;
     a.x = dr; a.w = st.wpack_d; a.bias = nullptr;
     a.y = st.up ? m->dfull : gnext;
@@ -444,6 +476,7 @@ int model_forward(ae_model* m, const void* params, const void* x, float snr_db, 
   const float sigma = (float)pow(10.0, -(double)snr_db / 20.0);
   m->have_forward = false;
   const size_t ns = P.steps.size();
+  AE_TRY(pack_all(m, prm, false, s));
   for (size_t i = 0; i < ns; ++i) {
     Step& st = P.steps[i];
     const void* in = step_input(m, i, x);
@@ -488,6 +521,7 @@ int model_backward(ae_model* m, const void* params, const void* x, const void* d
   size_t first_param = ns;
   for (size_t i = 0; i < ns; ++i)
     if (P.steps[i].kind == ST_CONV) { first_param = i; break; }
+  AE_TRY(pack_all(m, prm, true, s));
   for (size_t ii = ns; ii-- > first_param;) {
     Step& st = P.steps[ii];
     void* gnext = (g == m->grad_a) ? m->grad_b : m->grad_a;

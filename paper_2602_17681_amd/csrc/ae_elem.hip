@@ -75,6 +75,37 @@ __global__ void k_pack_weights(const float* __restrict__ w, T* __restrict__ wp, 
   }
 }
 
+// All layers of a pass in one launch: job j owns workgroups [first_block[j], first_block[j+1]),
+// 1024 packed elements per workgroup.
+template <typename T>
+__global__ void k_pack_weights_batch(PackBatch pb) {
+  int ji = 0;
+  while (ji + 1 < pb.n && (int64_t)blockIdx.x >= pb.job[ji + 1].first_block) ++ji;
+  const PackJob& J = pb.job[ji];
+  const int cout = J.cout, cin = J.cin, k = J.k;
+  const int64_t total = (int64_t)cout * cin * k * k;
+  const int64_t base = ((int64_t)blockIdx.x - J.first_block) * (NT * 4);
+  T* __restrict__ wp = (T*)J.wp;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int64_t i = base + u * NT + threadIdx.x;   // index in the PACKED layout: the stores coalesce
+    if (i >= total) break;
+    int64_t src;
+    if (!J.dgrad) {
+      int ci = (int)(i % cin); int64_t t = i / cin;
+      int s_ = (int)(t % k); t /= k;
+      int r = (int)(t % k); int co = (int)(t / k);
+      src = (((int64_t)co * cin + ci) * k + r) * k + s_;
+    } else {
+      int co = (int)(i % cout); int64_t t = i / cout;
+      int s_ = (int)(t % k); t /= k;
+      int r = (int)(t % k); int ci = (int)(t / k);
+      src = (((int64_t)co * cin + ci) * k + (k - 1 - r)) * k + (k - 1 - s_);
+    }
+    Store<T>::st(wp + i, J.w[src]);
+  }
+}
+
 // ---------------------------------------------------------------------------
 // Block-level helper: every thread holds NQ x VEC partial sums for channel group
 // `cg` (channels cbase + cg*VEC ...) accumulated over the rows of its row lane
@@ -600,6 +631,19 @@ int launch_to_f32_nchw(const void* in_nhwc, float* out_nchw, int64_t batch, int 
   // stored [hw][c] -> [c][hw]
   if (dtype == AE_BF16) return transpose_impl<bf16_t, float>(in_nhwc, out_nchw, batch, hw, c, s);
   return transpose_impl<float, float>(in_nhwc, out_nchw, batch, hw, c, s);
+}
+
+int launch_pack_weights_batch(PackBatch& pb, int dtype, hipStream_t s) {
+  if (pb.n <= 0) return AE_OK;
+  int64_t blocks = 0;
+  for (int j = 0; j < pb.n; ++j) {
+    pb.job[j].first_block = blocks;
+    const int64_t total = (int64_t)pb.job[j].cout * pb.job[j].cin * pb.job[j].k * pb.job[j].k;
+    blocks += (total + NT * 4 - 1) / (NT * 4);
+  }
+  if (blocks > 0x7FFFFFFF) return fail(AE_EINVAL, "pack_weights: too many elements");
+  DISPATCH_T(dtype, hipLaunchKernelGGL((k_pack_weights_batch<T>), dim3((unsigned)blocks), dim3(NT), 0, s, pb));
+  return launch_status("pack_weights_batch");
 }
 
 int launch_pack_weights(const float* w, void* wp, int cout, int cin, int k, int dtype, bool for_dgrad, hipStream_t s) {

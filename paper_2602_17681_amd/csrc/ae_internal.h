@@ -110,6 +110,11 @@ int launch_to_f32_nchw(const void* in_nhwc, float* out_nchw, int64_t batch, int 
 
 // weights
 int launch_pack_weights(const float* w, void* wp, int cout, int cin, int k, int dtype, bool for_dgrad, hipStream_t s);
+// several layers in one launch
+struct PackJob { const float* w; void* wp; int cout, cin, k, dgrad; int64_t first_block; };
+constexpr int kMaxPackJobs = 32;
+struct PackBatch { int n; PackJob job[kMaxPackJobs]; };
+int launch_pack_weights_batch(PackBatch& pb, int dtype, hipStream_t s);
 
 // convolution family (direct kernels; see ae_conv.hip for the MFMA ones)
 struct ConvArgs {
