@@ -208,11 +208,16 @@ __device__ __forceinline__ void igemm_epilogue(floatx16 (&acc)[BM / WGM / 32][BN
 // return in order, so "at most n outstanding" identifies which fragments have arrived.  An
 // empty asm with the fragment as in/out operand keeps the MFMAs after the wait.
 typedef __attribute__((address_space(3))) char lds_char;
+typedef __attribute__((address_space(3))) void lds_void_t;
 // 16 bytes per lane from a buffer straight into LDS: lane l writes lds_wave_base + 16*l
 // (offsets past the buffer's range deliver zeros like any buffer load)
 __device__ __forceinline__ void dma_load16(__amdgpu_buffer_rsrc_t rsrc, char* lds_wave_base, unsigned voffset) {
   typedef __attribute__((address_space(3))) void lds_void;
   __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)lds_wave_base, 16, voffset, 0, 0, 0);
+}
+// the same with a scalar (uniform) byte offset added to every lane's offset
+__device__ __forceinline__ void dma_load16s(__amdgpu_buffer_rsrc_t rsrc, char* lds_wave_base, unsigned voffset, unsigned soffset) {
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_t*)lds_wave_base, 16, voffset, soffset, 0, 0);
 }
 template <int I, int N, int STRIDE>
 struct LdsReadFrags {
@@ -1150,6 +1155,238 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
     }
 }
 
+// ---------------------------------------------------------------------------
+// Weight gradient of a 3x3 convolution, three taps (one filter row r) per workgroup (bf16).
+//
+// With one tap per workgroup the slabs of dY and of the shifted input stream through the vector
+// cache once per tap, and its 64 bytes per clock bound the kernel at about half the MFMA rate.
+// Here a workgroup owns BM output channels x 64 input channels x the three taps (r, s = 0..2): per
+// slab of 64 consecutive pixels it loads the dY slab once and ONE input patch — the slab's pixels
+// of row h + r - 1 plus one pixel of halo on each side — from which the three taps are shifted
+// views.  Slabs never straddle image rows (the host checks W % 64 == 0 or 64 % W == 0); a slab of
+// a narrow image (W = SW < 64) is 64/SW whole rows, each with its own halo.
+// LDS (three stages, filled by global-to-LDS loads): dY slab [64 px][BM] and patch
+// [64/SW segments][SW + 4 cells][64 ci]; cell 1 of a segment is the left halo, cells 2..SW+1 the
+// slab's pixels, cell SW+2 the right halo.  The 64-byte columns of a row are XOR-swizzled with
+// the pixel / cell index such that the transposing reads (8 pixels x 64 bytes per instruction)
+// spread evenly over the banks; for every fragment the swizzle is a per-lane constant, so all
+// reads are base + immediate.  Schedule per slab: wait for the next slab's loads, barrier, issue
+// the loads of the slab after that, then four K-steps of 16 pixels with the fragments of the
+// next K-step (the first of the next slab included) in flight behind the MFMAs.
+// ---------------------------------------------------------------------------
+typedef unsigned uint2v __attribute__((ext_vector_type(2)));
+struct TrFrag { uint2v lo, hi; };               // pixels 0..3 and 4..7 of a lane's channel
+
+template <int OFF>
+__device__ __forceinline__ void tr_read(TrFrag& f, unsigned addr, int row_bytes4 /* = 4 pixel rows */) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(f.lo) : "v"(addr), "n"(OFF));
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(f.hi) : "v"(addr + (unsigned)row_bytes4), "n"(OFF));
+#endif
+}
+__device__ __forceinline__ bf16x8 tr_value(TrFrag& f) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile("" : "+v"(f.lo), "+v"(f.hi));
+#endif
+  union { uint2v h[2]; bf16x8 v; } u;
+  u.h[0] = f.lo; u.h[1] = f.hi;
+  return u.v;
+}
+
+template <int BM, int SW>
+struct Wgrad3 {
+  static constexpr int BK = 64, SR = BK / SW, PCW = SW + 4, PCELLS = SR * PCW;
+  static constexpr int RBA = BM * 2;            // bytes per pixel of the dY slab (256 or 128)
+  static constexpr int A_BYTES = BK * RBA, A_PASSES = A_BYTES / 4096;
+  static constexpr int X_UNITS = (PCELLS * 128 + 1023) / 1024;      // 1 KB = one wave-wide load
+  static constexpr int XU = (X_UNITS + 3) / 4;   // units per wave
+  static constexpr int STAGE = A_BYTES + X_UNITS * 1024;
+  static constexpr int MI = BM / 64;            // 2x2 waves, wave tile (BM/2) x 32 per tap
+  // K-step ks covers slab pixels 16*ks .. 16*ks+15: first cell (tap s = 0, before the +1+s) of the patch
+  static constexpr int cell_base(int ks) { return ((ks * 16) / SW) * PCW + (ks * 16) % SW; }
+};
+
+// fragments of one K-step: MI of dY, three (taps) of the patch
+template <int BM, int SW, int KS>
+__device__ __forceinline__ void wgrad3_reads(TrFrag (&fa)[BM / 64], TrFrag (&fb)[3], unsigned a_addr, const unsigned (&b_addr)[3]) {
+  typedef Wgrad3<BM, SW> G;
+#pragma unroll
+  for (int i = 0; i < G::MI; ++i) {
+    // column i of the wave's co range: the swizzled column differs from a_addr's by (i << 6) XORed in
+    if (i == 0) tr_read<KS * 16 * G::RBA>(fa[0], a_addr, 4 * G::RBA);
+    else tr_read<KS * 16 * G::RBA>(fa[i], a_addr ^ 64u, 4 * G::RBA);
+  }
+#pragma unroll
+  for (int s_ = 0; s_ < 3; ++s_) tr_read<G::cell_base(KS) * 128>(fb[s_], b_addr[s_], 4 * 128);
+}
+
+template <int BM, int SW>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k_wgrad_row3(WgradParams p) {
+  typedef Wgrad3<BM, SW> G;
+  constexpr int MI = G::MI;
+  __shared__ __attribute__((aligned(1024))) char smem[3 * G::STAGE];   // XOR address arithmetic below needs the alignment
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  int b = xcd_logical_block((int)blockIdx.x, (int)gridDim.x);
+  const int r = b % 3; b /= 3;
+  const int tn = b % p.tiles_n; b /= p.tiles_n;
+  const int tm = b % p.tiles_m;
+  const int split = b / p.tiles_m;
+  const int co0 = tm * BM, ci0 = tn * 64;
+  const int Hin = p.Hc >> p.up, Win = p.Wc >> p.up;
+  const int64_t m_begin = (int64_t)split * p.rows_per_split;
+  const int64_t m_end = (m_begin + p.rows_per_split < p.M) ? m_begin + p.rows_per_split : p.M;
+  const int KT = (int)((m_end - m_begin) / G::BK);
+  const __amdgpu_buffer_rsrc_t rX = make_rsrc(p.x, p.x_bytes);
+  const __amdgpu_buffer_rsrc_t rDY = make_rsrc(p.dy, p.dy_bytes);
+
+  // ---- loaders.  dY: slot q = pass*256 + tid of the linear slab: pixel q / CPP, chunk q % CPP
+  constexpr int CPP = G::RBA / 16;
+  unsigned a_voff[G::A_PASSES];
+#pragma unroll
+  for (int i = 0; i < G::A_PASSES; ++i) {
+    const int q = i * 256 + tid;
+    const int px = q / CPP, chunk = q % CPP;
+    const int sw = G::RBA == 256 ? (px & 3) : ((px >> 1) & 1);
+    a_voff[i] = (unsigned)px * (unsigned)(p.Cout * 2) + (unsigned)(co0 * 2) + (unsigned)((chunk ^ (sw << 2)) * 16);
+  }
+  // patch: unit u = wave + 4*k of 1 KB: slot q = u*64 + lane: cell q / 8, chunk q % 8
+  int x_seg[G::XU], x_pc[G::XU];
+  unsigned x_chunk[G::XU];
+  bool x_cell_ok[G::XU];
+#pragma unroll
+  for (int k = 0; k < G::XU; ++k) {
+    const int q = (wave + 4 * k) * 64 + lane;
+    const int cell = q >> 3;
+    x_seg[k] = cell / G::PCW;
+    x_pc[k] = cell - x_seg[k] * G::PCW;
+    x_chunk[k] = (unsigned)(((q & 7) ^ (((cell >> 1) & 1) << 2)) * 16) + (unsigned)(ci0 * 2);
+    x_cell_ok[k] = cell < G::PCELLS && x_pc[k] >= 1 && x_pc[k] <= SW + 2;
+  }
+  // coordinates of the next slab to load (uniform)
+  unsigned a_soff = (unsigned)m_begin * (unsigned)(p.Cout * 2);
+  int w0 = (int)((unsigned)m_begin % (unsigned)p.Wc);
+  int h = (int)(((unsigned)m_begin / (unsigned)p.Wc) % (unsigned)p.Hc);
+  int n = (int)((unsigned)m_begin / ((unsigned)p.Wc * (unsigned)p.Hc));
+  const unsigned cin_bytes = (unsigned)(p.Cin * 2);
+#define WGRAD3_DMA(STG)                                                                                      \
+  {                                                                                                          \
+    char* const da = smem + (STG) * G::STAGE + wave * 1024;                                                  \
+    _Pragma("unroll") for (int i = 0; i < G::A_PASSES; ++i)                                                  \
+        dma_load16s(rDY, da + i * 4096, a_voff[i], a_soff);                                                  \
+    _Pragma("unroll") for (int k = 0; k < G::XU; ++k) {                                                      \
+      if (wave + 4 * k < G::X_UNITS) {                                                                       \
+        const int row = h + x_seg[k] + r - 1, col = w0 + x_pc[k] - 2;                                        \
+        const bool ok = x_cell_ok[k] && row >= 0 && row < p.Hc && col >= 0 && col < p.Wc;                    \
+        const unsigned pix = ((unsigned)n * (unsigned)Hin + (unsigned)(row >> p.up)) * (unsigned)Win + (unsigned)(col >> p.up); \
+        dma_load16(rX, smem + (STG) * G::STAGE + G::A_BYTES + (wave + 4 * k) * 1024, ok ? pix * cin_bytes + x_chunk[k] : kOob); \
+      }                                                                                                      \
+    }                                                                                                        \
+    a_soff += (unsigned)(G::BK * p.Cout * 2);                                                                \
+    if (SW < 64) { h += G::SR; if (h == p.Hc) { h = 0; ++n; } }                                              \
+    else { w0 += 64; if (w0 == p.Wc) { w0 = 0; if (++h == p.Hc) { h = 0; ++n; } } }                          \
+  }
+
+  // ---- fragment addresses (per-lane constants).  Transposing read: within 16 lanes, lane 4*j+q
+  // addresses 4 channels (4q..) of pixel j; 16-lane group G: channels +16*(G&1), pixels +8*(G>>1)
+  const int grp = lane >> 4, sl = lane & 15;
+  const int lp = 8 * (grp >> 1) + (sl >> 2);
+  const unsigned lds0 = (unsigned)(size_t)(lds_char*)smem;
+  const int a_col = G::RBA == 256 ? (2 * wm) : wm;                       // 64-byte column of the wave's first 32 channels
+  const int a_sw = G::RBA == 256 ? (lp & 3) : ((lp >> 1) & 1);
+  const unsigned a_lane = (unsigned)(lp * G::RBA + ((a_col ^ a_sw) << 6) + 32 * (grp & 1) + 8 * (sl & 3));
+  unsigned b_lane[3];
+#pragma unroll
+  for (int s_ = 0; s_ < 3; ++s_) {
+    const int cell = 1 + s_ + lp;                // + cell_base(ks) (a multiple of 4) + 4 for the second half
+    b_lane[s_] = (unsigned)(G::A_BYTES + cell * 128 + ((wn ^ ((cell >> 1) & 1)) << 6) + 32 * (grp & 1) + 8 * (sl & 3));
+  }
+
+  floatx16 acc[3][MI];
+#pragma unroll
+  for (int s_ = 0; s_ < 3; ++s_)
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[s_][i][e] = 0.0f;
+
+  TrFrag fa0[MI], fb0[3], fa1[MI], fb1[3];
+  constexpr int NR = 2 * (MI + 3);               // LDS reads per K-step
+#define WGRAD3_MMA(FA, FB)                                                                                   \
+  {                                                                                                          \
+    bf16x8 av[MI];                                                                                           \
+    _Pragma("unroll") for (int i = 0; i < MI; ++i) av[i] = tr_value(FA[i]);                                  \
+    _Pragma("unroll") for (int s_ = 0; s_ < 3; ++s_) {                                                       \
+      const bf16x8 bv = tr_value(FB[s_]);                                                                    \
+      _Pragma("unroll") for (int i = 0; i < MI; ++i)                                                         \
+          acc[s_][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv, acc[s_][i], 0, 0, 0);              \
+    }                                                                                                        \
+    __builtin_amdgcn_sched_barrier(0);                                                                       \
+  }
+#define LGKM_WAIT(N) asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N))
+
+  // prologue: slabs 0 and 1 in flight, fragments of (slab 0, K-step 0)
+  WGRAD3_DMA(0);
+  if (KT > 1) WGRAD3_DMA(1);
+  __builtin_amdgcn_s_waitcnt(vm_imm(0));
+  __builtin_amdgcn_s_barrier();
+  {
+    unsigned ba[3];
+#pragma unroll
+    for (int s_ = 0; s_ < 3; ++s_) ba[s_] = lds0 + b_lane[s_];
+    wgrad3_reads<BM, SW, 0>(fa0, fb0, lds0 + a_lane, ba);
+  }
+  int cur = 0;
+  for (int t = 0; t < KT; ++t) {
+    // the loads of slab t+1 (issued one slab ago) are the only ones outstanding
+    __builtin_amdgcn_s_waitcnt(vm_imm(0));
+    __builtin_amdgcn_s_barrier();
+    const int nxt = cur == 2 ? 0 : cur + 1;
+    if (t + 2 < KT) { const int st2 = nxt == 2 ? 0 : nxt + 1; WGRAD3_DMA(st2); }
+    const unsigned sa = lds0 + (unsigned)(cur * G::STAGE) + a_lane;
+    unsigned sb[3], nb[3];
+#pragma unroll
+    for (int s_ = 0; s_ < 3; ++s_) { sb[s_] = lds0 + (unsigned)(cur * G::STAGE) + b_lane[s_]; nb[s_] = lds0 + (unsigned)(nxt * G::STAGE) + b_lane[s_]; }
+    const unsigned na = lds0 + (unsigned)(nxt * G::STAGE) + a_lane;
+#if defined(__HIP_DEVICE_COMPILE__)
+    wgrad3_reads<BM, SW, 1>(fa1, fb1, sa, sb);
+    LGKM_WAIT(NR);
+    WGRAD3_MMA(fa0, fb0)
+    wgrad3_reads<BM, SW, 2>(fa0, fb0, sa, sb);
+    LGKM_WAIT(NR);
+    WGRAD3_MMA(fa1, fb1)
+    wgrad3_reads<BM, SW, 3>(fa1, fb1, sa, sb);
+    LGKM_WAIT(NR);
+    WGRAD3_MMA(fa0, fb0)
+    if (t + 1 < KT) {
+      wgrad3_reads<BM, SW, 0>(fa0, fb0, na, nb);
+      LGKM_WAIT(NR);
+    } else {
+      LGKM_WAIT(0);
+    }
+    WGRAD3_MMA(fa1, fb1)
+#endif
+    cur = nxt;
+  }
+#undef WGRAD3_DMA
+#undef WGRAD3_MMA
+#undef LGKM_WAIT
+
+  // partial[split][co][(r*3 + s)*Cin + ci]
+  float* __restrict__ P = p.partial + (int64_t)split * p.Cout * p.K;
+  const int col_lane = lane & 31, row_lane = (lane >> 5) * 4;
+  const int ci = ci0 + wn * 32 + col_lane;
+#pragma unroll
+  for (int s_ = 0; s_ < 3; ++s_)
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int co = co0 + wm * (BM / 2) + i * 32 + (e >> 2) * 8 + row_lane + (e & 3);
+        P[(int64_t)co * p.K + (r * 3 + s_) * p.Cin + ci] = acc[s_][i][e];
+      }
+}
+
 // dW[co][ci][r][s] = sum over splits of partial[split][co][(r,s,ci)].  A workgroup owns 64
 // consecutive outputs; wave v sums splits v, v+4, ... (independent loads, several in flight),
 // then the four waves are combined in a fixed order.
@@ -1177,10 +1414,29 @@ __global__ __launch_bounds__(256) void k_wgrad_reduce(const float* __restrict__ 
   }
 }
 
-struct WgradPlan { int bm, bn, bk, tiles_m, tiles_n, splits, rows_per_split; };   // bk = 0: generic kernel
+struct WgradPlan { int bm, bn, bk, tiles_m, tiles_n, splits, rows_per_split, row3; };   // bk = 0: generic kernel; row3: three taps per workgroup
 
-WgradPlan plan_wgrad(int cout, int cin, int k, int64_t rows, int wc, int es) {
+WgradPlan plan_wgrad(int cout, int cin, int k, int64_t rows, int wc, int es, int hc = 0) {
   WgradPlan w;
+  w.row3 = 0;
+  if (es == 2 && k == 3 && hc > 0 && (wc % 64 == 0 || (wc >= 16 && 64 % wc == 0)) && ((int64_t)hc * wc) % 64 == 0) {
+    w.row3 = 1;
+    w.bm = cout % 128 == 0 ? 128 : 64;
+    w.bn = 64;
+    w.bk = 64;
+    w.tiles_m = cout / w.bm;
+    w.tiles_n = cin / 64;
+    const int64_t groups = (int64_t)w.tiles_m * w.tiles_n * 3;
+    int64_t splits = (512 + groups - 1) / groups;       // two workgroups per compute unit fit: one round
+    const int64_t max_splits = (rows + 511) / 512;
+    if (splits > max_splits) splits = max_splits;
+    if (splits < 1) splits = 1;
+    int64_t rps = (rows + splits - 1) / splits;
+    rps = (rps + 63) / 64 * 64;
+    w.rows_per_split = (int)rps;
+    w.splits = (int)((rows + rps - 1) / rps);
+    return w;
+  }
   w.bm = cout % 128 == 0 ? 128 : 64;
   w.bn = cin % 128 == 0 ? 128 : 64;
   if (w.bm == 64 && w.bn == 64) w.bn = 64;
@@ -1213,15 +1469,16 @@ bool wgrad_mfma_supported(const WgradArgs& a) {
   return rows < 0x7FFFFFFF;
 }
 
-int64_t wgrad_mfma_workspace_floats(int cout, int cin, int k, int64_t rows) {
-  const WgradPlan w = plan_wgrad(cout, cin, k, rows, 0, 2);
-  return (int64_t)w.splits * cout * cin * k * k;
+int64_t wgrad_mfma_workspace_floats(const WgradArgs& a) {
+  const int64_t rows = (int64_t)a.n * a.hc * a.wc;
+  const WgradPlan w = plan_wgrad(a.cout, a.cin, a.k, rows, a.wc, (int)dtype_size(a.dtype), a.hc);
+  return (int64_t)w.splits * a.cout * a.cin * a.k * a.k;
 }
 
 int launch_wgrad_mfma(const WgradArgs& a, float* workspace, hipStream_t s) {
   if (!wgrad_mfma_supported(a)) return fail(AE_EINVAL, "wgrad_mfma: shape not supported");
   const int64_t rows = (int64_t)a.n * a.hc * a.wc;
-  const WgradPlan w = plan_wgrad(a.cout, a.cin, a.k, rows, a.wc, (int)dtype_size(a.dtype));
+  const WgradPlan w = plan_wgrad(a.cout, a.cin, a.k, rows, a.wc, (int)dtype_size(a.dtype), a.hc);
   WgradParams p;
   p.x = a.x; p.dy = a.dy; p.partial = workspace;
   p.M = rows; p.Cout = a.cout; p.Cin = a.cin; p.Hc = a.hc; p.Wc = a.wc; p.ksz = a.k; p.up = a.up;
@@ -1236,7 +1493,7 @@ int launch_wgrad_mfma(const WgradArgs& a, float* workspace, hipStream_t s) {
     while ((1 << p.log_w) < a.wc) ++p.log_w;
     while ((1 << p.log_h) < a.hc) ++p.log_h;
   }
-  const int64_t blocks = (int64_t)w.splits * w.tiles_m * w.tiles_n * a.k * a.k;
+  const int64_t blocks = (int64_t)w.splits * w.tiles_m * w.tiles_n * (w.row3 ? 3 : a.k * a.k);
   if (blocks > 0x7FFFFFFF) return fail(AE_EINVAL, "wgrad_mfma: grid too large");
   dim3 grid((unsigned)blocks);
 #define WGRAD_LAUNCH_P(T, P2)                                                                           \
@@ -1258,7 +1515,18 @@ int launch_wgrad_mfma(const WgradArgs& a, float* workspace, hipStream_t s) {
     else if (w.bn == 128) hipLaunchKernelGGL((k_wgrad_rows<T, 64, 128, BKV>), grid, dim3(256), 0, s, p); \
     else hipLaunchKernelGGL((k_wgrad_rows<T, 64, 64, BKV>), grid, dim3(256), 0, s, p);                  \
   } while (0)
-  if (w.bk && a.dtype == AE_BF16) { if (w.bk == 64) WGRAD_ROWS(bf16_t, 64); else WGRAD_ROWS(bf16_t, 32); }
+  if (w.row3) {
+    const int sw = a.wc < 64 ? a.wc : 64;
+#define WGRAD_ROW3(BMV)                                                                                 \
+  do {                                                                                                  \
+    if (sw == 64) hipLaunchKernelGGL((k_wgrad_row3<BMV, 64>), grid, dim3(256), 0, s, p);                \
+    else if (sw == 32) hipLaunchKernelGGL((k_wgrad_row3<BMV, 32>), grid, dim3(256), 0, s, p);           \
+    else hipLaunchKernelGGL((k_wgrad_row3<BMV, 16>), grid, dim3(256), 0, s, p);                         \
+  } while (0)
+    if (w.bm == 128) WGRAD_ROW3(128); else WGRAD_ROW3(64);
+#undef WGRAD_ROW3
+  }
+  else if (w.bk && a.dtype == AE_BF16) { if (w.bk == 64) WGRAD_ROWS(bf16_t, 64); else WGRAD_ROWS(bf16_t, 32); }
   else if (w.bk) { if (w.bk == 32) WGRAD_ROWS(float, 32); else WGRAD_ROWS(float, 16); }
   else if (a.dtype == AE_BF16) WGRAD_LAUNCH(bf16_t);
   else WGRAD_LAUNCH(float);

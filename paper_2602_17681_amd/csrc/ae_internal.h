@@ -134,7 +134,7 @@ struct WgradArgs {
 };
 int launch_wgrad_direct(const WgradArgs& a, hipStream_t s);
 bool wgrad_mfma_supported(const WgradArgs& a);
-int64_t wgrad_mfma_workspace_floats(int cout, int cin, int k, int64_t rows);
+int64_t wgrad_mfma_workspace_floats(const WgradArgs& a);
 int launch_wgrad_mfma(const WgradArgs& a, float* workspace, hipStream_t s);  // overwrites dw (no zeroing needed)
 
 // 3x3 convolutions with 1..4 channels on one side (first / last layer); see ae_conv_thin.hip

@@ -281,7 +281,7 @@ int build_plan(const char* spec, int batch, int dtype, int bn_mode, Plan* plan) 
                                             thin_wgrad_mfma_workspace_floats(batch, st.hin, st.win, st.cin));
       }
       else if (wgrad_mfma_supported(wa))
-        plan->max_wgrad_floats = std::max(plan->max_wgrad_floats, wgrad_mfma_workspace_floats(st.cout, st.cin, st.k, rows));
+        plan->max_wgrad_floats = std::max(plan->max_wgrad_floats, wgrad_mfma_workspace_floats(wa));
       if (st.thin == 2)
         plan->max_partial_floats = std::max(plan->max_partial_floats,
                                             B * plane_sums_split((int64_t)st.hc * st.wc) * 2 * (int64_t)st.cout);
