@@ -115,14 +115,21 @@ int pack_all(ae_model* m, const float* params, bool dgrad, hipStream_t s) {
   for (const Step& st : P.steps) {
     const bool want = dgrad ? needs_dgrad_pack(st) : needs_fwd_pack(P, st);
     if (!want) continue;
+    if (st.k == 1 && (int64_t)st.cout * st.cin >= (1 << 20)) {
+      // big fully-connected layers: bandwidth-bound conversion / transpose kernels of their own
+      TIMED(0, dgrad ? "bwd.pack_weights_fc" : "fwd.pack_weights_fc", 0.0,
+            (double)st.cout * st.cin * (4.0 + (double)dtype_size(P.dtype)),
+            launch_pack_weights_1x1(params + st.w_off, dgrad ? st.wpack_d : st.wpack, st.cout, st.cin, P.dtype, dgrad, s));
+      continue;
+    }
     if (pb.n == kMaxPackJobs) return AE_OK;      // too many layers: fall back to per-layer packing
     PackJob& j = pb.job[pb.n++];
     j.w = params + st.w_off; j.wp = dgrad ? st.wpack_d : st.wpack;
     j.cout = st.cout; j.cin = st.cin; j.k = st.k; j.dgrad = dgrad ? 1 : 0; j.first_block = 0;
     bytes += (double)st.cout * st.cin * st.k * st.k * (4.0 + (double)dtype_size(P.dtype));
   }
-  if (pb.n == 0) return AE_OK;
-  TIMED(0, dgrad ? "bwd.pack_weights_all" : "fwd.pack_weights_all", 0.0, bytes, launch_pack_weights_batch(pb, P.dtype, s));
+  if (pb.n > 0)
+    TIMED(0, dgrad ? "bwd.pack_weights_all" : "fwd.pack_weights_all", 0.0, bytes, launch_pack_weights_batch(pb, P.dtype, s));
   m->packed_in_batch = true;
   return AE_OK;
 }
@@ -165,6 +172,8 @@ int forward_conv(ae_model* m, int si, Step& st, const float* params, const void*
   a.dtype = P.dtype;
   a.partial = nullptr;
   a.y_aux = second_pass ? nullptr : st.aux;
+  a.splitk_ws = m->wgrad_ws;
+  a.splitk_floats = P.max_wgrad_floats;
   int nblk = 0;
   const double conv_flops = 2.0 * raw_el * st.cin * st.k * st.k;
   const double conv_bytes = (in_el + raw_el + wel) * es;
@@ -322,6 +331,8 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
     a.y = st.up ? m->dfull : gnext;
     a.n = P.batch; a.hc = st.hc; a.wc = st.wc; a.cin = st.cout; a.cout = st.cin; a.k = st.k; a.up = 0;
     a.act = ACT_NONE; a.dtype = P.dtype; a.partial = nullptr; a.y_aux = nullptr;
+    a.splitk_ws = m->wgrad_ws;                   // the weight gradient of this step is done with it
+    a.splitk_floats = P.max_wgrad_floats;
     const double full_el = (double)rows * st.cin;
     if (conv_mfma_supported(a))
       TIMED(si, "bwd.dgrad_mfma", conv_flops, (raw_el + full_el + wel) * es, launch_conv_mfma(a, s));

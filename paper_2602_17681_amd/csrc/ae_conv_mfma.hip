@@ -30,6 +30,11 @@ struct IgemmParams {
   int act;
   int tiles_n;
   unsigned x_bytes, w_bytes;   // sizes of the two operand tensors (buffer range checks)
+  // split-K (layers with too few output tiles to fill the chip): workgroup (split, tile) works on
+  // K slabs [split*slabs_per_split, ...) and writes its fp32 tile to split_out[split][M][N];
+  // k_splitk_finish sums the splits and applies bias / rounding / activation
+  int tiles_mn, slabs_per_split;
+  float* split_out;
 };
 
 // ---------------------------------------------------------------------------
@@ -311,7 +316,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
-  const int lb = xcd_logical_block((int)blockIdx.x, (int)gridDim.x);
+  const int lb0 = xcd_logical_block((int)blockIdx.x, (int)gridDim.x);
+  const int split = INTERIOR ? 0 : lb0 / p.tiles_mn;
+  const int lb = INTERIOR ? lb0 : lb0 - split * p.tiles_mn;
   const int tile_n = lb % p.tiles_n;
   const int64_t tile_m = lb / p.tiles_n;
   const int64_t m0 = tile_m * BM;
@@ -346,8 +353,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
     b_off[i] = row < p.N ? (unsigned)row * (unsigned)p.K * (unsigned)ES + (unsigned)gchunk * 16u : kOob;
   }
 
-  int rs = 0, ci0 = 0;                          // filter tap and first channel of the next slab to load
-  unsigned kbyte = 0;                           // byte offset of the next slab inside a weight row
+  const int kt0 = INTERIOR ? 0 : split * p.slabs_per_split;             // first K slab of this workgroup
+  int rs = (kt0 * BK) / p.Cin, ci0 = (kt0 * BK) % p.Cin;                // filter tap and first channel of the next slab to load
+  unsigned kbyte = (unsigned)(kt0 * BKB);       // byte offset of the next slab inside a weight row
 #define IGEMM_TAP()                                                                                          \
   {                                                                                                          \
     const int r_ = rs / p.ksz, s_ = rs - r_ * p.ksz;                                                         \
@@ -405,7 +413,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-  const int KT = p.K / BK;
+  const int KT = INTERIOR ? p.K / BK : min(p.K / BK - kt0, p.slabs_per_split);
+  if (ci0 != 0) IGEMM_TAP();                     // a split that starts inside a tap (the loaders compute a tap's offsets at its first slab)
   if constexpr (DMA) {
     constexpr int L = A_CHUNKS + B_CHUNKS;       // loads per thread and slab
     static_assert(RSTEP * BKB == 4096, "one pass of the loader covers 4 KB");
@@ -468,7 +477,40 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
 #undef IGEMM_STORE
 #undef IGEMM_COMPUTE
 
+  if constexpr (!INTERIOR) {
+    if (p.split_out) {
+      float* __restrict__ P = p.split_out + (int64_t)split * p.M * p.N;
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+          const int col = n0 + wn * WN + j * 32 + (lane & 31);
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const int64_t m = m0 + wm * WM + i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+            if (m < p.M && col < p.N) P[m * p.N + col] = acc[i][j][e];
+          }
+        }
+      return;
+    }
+  }
   igemm_epilogue<T, BM, BN, WGM, WGN, INTERIOR>(acc, p, smem, sRed, m0, n0, tile_m);
+}
+
+// y = act(round(sum over splits of partial[split] + bias)) for split-K launches
+template <typename T>
+__global__ void k_splitk_finish(const float* __restrict__ partial, int splits, int64_t M, int N, const float* __restrict__ bias,
+                                int act, T* __restrict__ y, float* __restrict__ y_aux) {
+  const int64_t total = M * N;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    float acc = 0.0f;
+#pragma unroll 8
+    for (int sp = 0; sp < splits; ++sp) acc += partial[(int64_t)sp * total + i];
+    if (bias) acc += bias[(int)(i % N)];
+    const float a = apply_act(round_to_storage<T>(acc), act);
+    Store<T>::st(y + i, a);
+    if (y_aux) y_aux[i] = a;
+  }
 }
 
 // wait until at most N LDS reads are outstanding, then hand the fragments to the compiler
@@ -741,6 +783,25 @@ int conv_partial_rows(const ConvArgs& a, bool mfma) {
   return pick_tile((int64_t)a.n * a.hc * a.wc, a.cout, a.cin, (int)dtype_size(a.dtype)).bm;
 }
 
+// Split-K: layers with fewer than 128 output tiles (small batch x fully-connected) and a long K.
+static int conv_mfma_splits(const ConvArgs& a) {
+  if (a.partial || !conv_mfma_supported(a) || conv3_patch_usable(a)) return 1;
+  const int es = (int)dtype_size(a.dtype);
+  const int64_t M = (int64_t)a.n * a.hc * a.wc;
+  const IgemmTile t = pick_tile(M, a.cout, a.cin, es);
+  const int64_t tiles = ((M + t.bm - 1) / t.bm) * ((a.cout + t.bn - 1) / t.bn);
+  const int64_t KT = (int64_t)a.k * a.k * a.cin * es / t.bkb;
+  if (tiles >= 128 || KT < 16) return 1;
+  int64_t splits = (512 + tiles - 1) / tiles;
+  if (splits > KT / 4) splits = KT / 4;
+  return splits < 1 ? 1 : (int)splits;
+}
+
+int64_t conv_mfma_splitk_floats(const ConvArgs& a) {
+  const int splits = conv_mfma_splits(a);
+  return splits > 1 ? (int64_t)splits * a.n * a.hc * a.wc * a.cout : 0;
+}
+
 int launch_conv_mfma(const ConvArgs& a, hipStream_t s) {
   if (!conv_mfma_supported(a)) return fail(AE_EINVAL, "conv_mfma: shape not supported");
   const int es = (int)dtype_size(a.dtype);
@@ -775,8 +836,15 @@ int launch_conv_mfma(const ConvArgs& a, hipStream_t s) {
   const IgemmTile t = pick_tile(p.M, a.cout, a.cin, es);
   p.tiles_n = (a.cout + t.bn - 1) / t.bn;
   const int64_t tiles_m = (p.M + t.bm - 1) / t.bm;
-  dim3 grid((unsigned)(tiles_m * p.tiles_n));
-  const bool interior = p.M % t.bm == 0 && p.N % t.bn == 0 && !a.y_aux && a.act != ACT_SIGMOID &&
+  const int KT = (int)((int64_t)p.K * es / t.bkb);
+  int splits = conv_mfma_splits(a);
+  if (splits > 1 && (!a.splitk_ws || (int64_t)splits * p.M * p.N > a.splitk_floats)) splits = 1;
+  p.tiles_mn = (int)(tiles_m * p.tiles_n);
+  p.slabs_per_split = (KT + splits - 1) / splits;
+  splits = (KT + p.slabs_per_split - 1) / p.slabs_per_split;
+  p.split_out = splits > 1 ? a.splitk_ws : nullptr;
+  dim3 grid((unsigned)(tiles_m * p.tiles_n * splits));
+  const bool interior = splits == 1 && p.M % t.bm == 0 && p.N % t.bn == 0 && !a.y_aux && a.act != ACT_SIGMOID &&
                         !(a.partial && a.act != ACT_NONE);
 #define IGEMM_LAUNCH_K(T, BMV, BNV, GM, GN, KB)                                                        \
   do {                                                                                                 \
@@ -800,7 +868,19 @@ int launch_conv_mfma(const ConvArgs& a, hipStream_t s) {
 #undef IGEMM_LAUNCH_K
 #undef IGEMM_LAUNCH
 #undef IGEMM_LAUNCH_T
-  return launch_status("conv_mfma");
+  AE_TRY(launch_status("conv_mfma"));
+  if (splits > 1) {
+    int64_t g = (p.M * p.N + 255) / 256;
+    if (g > 8192) g = 8192;
+    if (a.dtype == AE_BF16)
+      hipLaunchKernelGGL((k_splitk_finish<bf16_t>), dim3((unsigned)g), dim3(256), 0, s, a.splitk_ws, splits, p.M, p.N, a.bias,
+                         a.act, (bf16_t*)a.y, a.y_aux);
+    else
+      hipLaunchKernelGGL((k_splitk_finish<float>), dim3((unsigned)g), dim3(256), 0, s, a.splitk_ws, splits, p.M, p.N, a.bias,
+                         a.act, (float*)a.y, a.y_aux);
+    return launch_status("splitk_finish");
+  }
+  return AE_OK;
 }
 
 }  // namespace ae
@@ -1480,7 +1560,9 @@ int launch_wgrad_mfma(const WgradArgs& a, float* workspace, hipStream_t s) {
   const int64_t rows = (int64_t)a.n * a.hc * a.wc;
   const WgradPlan w = plan_wgrad(a.cout, a.cin, a.k, rows, a.wc, (int)dtype_size(a.dtype), a.hc);
   WgradParams p;
-  p.x = a.x; p.dy = a.dy; p.partial = workspace;
+  // a 1x1 layer that needs no split: the partial layout [co][ci] is the canonical one
+  const bool direct = w.splits == 1 && a.k == 1;
+  p.x = a.x; p.dy = a.dy; p.partial = direct ? a.dw_canonical : workspace;
   p.M = rows; p.Cout = a.cout; p.Cin = a.cin; p.Hc = a.hc; p.Wc = a.wc; p.ksz = a.k; p.up = a.up;
   p.tiles_m = w.tiles_m; p.tiles_n = w.tiles_n; p.rows_per_split = w.rows_per_split;
   p.K = a.k * a.k * a.cin;
@@ -1534,6 +1616,7 @@ int launch_wgrad_mfma(const WgradArgs& a, float* workspace, hipStream_t s) {
 #undef WGRAD_LAUNCH_P
 #undef WGRAD_LAUNCH
   AE_TRY(launch_status("wgrad_mfma"));
+  if (direct) return AE_OK;
   const int64_t total = (int64_t)a.cout * a.cin * a.k * a.k;
   const int64_t g = (total + 63) / 64;
   hipLaunchKernelGGL(k_wgrad_reduce, dim3((unsigned)g), dim3(256), 0, s, workspace, w.splits, a.cout, a.cin, a.k * a.k,

@@ -145,12 +145,14 @@ __global__ void k_col_stats(const T* __restrict__ x, int64_t rows, int rpb, int 
   const int64_t r0 = (int64_t)blockIdx.x * rpb;
   const int64_t r1 = r0 + rpb < rows ? r0 + rpb : rows;
   float* pb = partial + (int64_t)blockIdx.x * 2 * C;
-  for (int cbase = 0; cbase < C; cbase += tpr * VEC) {
+  {
+    const int cbase = blockIdx.y * tpr * VEC;      // grid.y covers the columns
     float acc[2][VEC];
 #pragma unroll
     for (int v = 0; v < VEC; ++v) acc[0][v] = acc[1][v] = 0.0f;
     const int c = cbase + cg * VEC;
     if (active && c < C) {
+#pragma unroll 4
       for (int64_t r = r0 + rl; r < r1; r += nrl) {
         float v[VEC];
         if (VEC == 1) v[0] = Store<T>::ld(x + r * C + c);
@@ -633,6 +635,31 @@ int launch_to_f32_nchw(const void* in_nhwc, float* out_nchw, int64_t batch, int 
   return transpose_impl<float, float>(in_nhwc, out_nchw, batch, hw, c, s);
 }
 
+// 1x1 layers: the forward packing is a plain conversion, the input-gradient packing a transpose
+template <typename T>
+__global__ void k_convert_f32(const float* __restrict__ w, T* __restrict__ wp, int64_t n) {
+  const int64_t n8 = n / 8;
+#pragma unroll 2
+  for (int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x; i < n8; i += (int64_t)gridDim.x * NT) {
+    const float4 a = *reinterpret_cast<const float4*>(w + i * 8), b = *reinterpret_cast<const float4*>(w + i * 8 + 4);
+    Store<T>::st(wp + i * 8 + 0, a.x); Store<T>::st(wp + i * 8 + 1, a.y); Store<T>::st(wp + i * 8 + 2, a.z); Store<T>::st(wp + i * 8 + 3, a.w);
+    Store<T>::st(wp + i * 8 + 4, b.x); Store<T>::st(wp + i * 8 + 5, b.y); Store<T>::st(wp + i * 8 + 6, b.z); Store<T>::st(wp + i * 8 + 7, b.w);
+  }
+  for (int64_t i = n8 * 8 + (int64_t)blockIdx.x * NT + threadIdx.x; i < n; i += (int64_t)gridDim.x * NT) Store<T>::st(wp + i, w[i]);
+}
+
+int launch_pack_weights_1x1(const float* w, void* wp, int cout, int cin, int dtype, bool for_dgrad, hipStream_t s) {
+  if (for_dgrad) {
+    if (dtype == AE_BF16) return transpose_impl<float, bf16_t>(w, wp, 1, cout, cin, s);
+    return transpose_impl<float, float>(w, wp, 1, cout, cin, s);
+  }
+  const int64_t n = (int64_t)cout * cin;
+  const bool aligned = (((uintptr_t)w | (uintptr_t)wp) & 15) == 0;
+  if (!aligned) return launch_pack_weights(w, wp, cout, cin, 1, dtype, false, s);
+  DISPATCH_T(dtype, hipLaunchKernelGGL((k_convert_f32<T>), dim3(grid_for(n, NT * 8, 16384)), dim3(NT), 0, s, w, (T*)wp, n));
+  return launch_status("convert_f32");
+}
+
 int launch_pack_weights_batch(PackBatch& pb, int dtype, hipStream_t s) {
   if (pb.n <= 0) return AE_OK;
   int64_t blocks = 0;
@@ -656,8 +683,12 @@ int launch_pack_weights(const float* w, void* wp, int cout, int cin, int k, int 
 int launch_col_stats(const void* x, int64_t rows, int c, int dtype, float* partial, hipStream_t s) {
   const int rpb = reduce_rows_per_block(rows);
   const int nblocks = reduce_blocks(rows);
-  DISPATCH_T_VEC(dtype, c, hipLaunchKernelGGL((k_col_stats<T, VEC>), dim3(nblocks), dim3(NT), 0, s, (const T*)x, rows,
-                                              rpb, c, partial));
+  DISPATCH_T_VEC(dtype, c, {
+    const int groups = (c + VEC - 1) / VEC;
+    const int tpr = groups < NT ? groups : NT;
+    hipLaunchKernelGGL((k_col_stats<T, VEC>), dim3(nblocks, (c + tpr * VEC - 1) / (tpr * VEC)), dim3(NT), 0, s, (const T*)x,
+                       rows, rpb, c, partial);
+  });
   return launch_status("col_stats");
 }
 

@@ -115,6 +115,7 @@ struct PackJob { const float* w; void* wp; int cout, cin, k, dgrad; int64_t firs
 constexpr int kMaxPackJobs = 32;
 struct PackBatch { int n; PackJob job[kMaxPackJobs]; };
 int launch_pack_weights_batch(PackBatch& pb, int dtype, hipStream_t s);
+int launch_pack_weights_1x1(const float* w, void* wp, int cout, int cin, int dtype, bool for_dgrad, hipStream_t s);
 
 // convolution family (direct kernels; see ae_conv.hip for the MFMA ones)
 struct ConvArgs {
@@ -122,7 +123,10 @@ struct ConvArgs {
   int n, hc, wc, cin, cout, k, up, act, dtype;
   float* partial;  // nullable: per-row-block column sums / sums of squares of the fp32 result
   float* y_aux;    // nullable: binary32 copy of y (after the activation)
+  float* splitk_ws = nullptr;      // scratch for split-K partial tiles (conv_mfma_splitk_floats), nullable: no split-K
+  int64_t splitk_floats = 0;
 };
+int64_t conv_mfma_splitk_floats(const ConvArgs& a);   // 0: this layer runs without split-K
 int launch_conv_direct(const ConvArgs& a, hipStream_t s);
 bool conv_mfma_supported(const ConvArgs& a);
 int launch_conv_mfma(const ConvArgs& a, hipStream_t s);

@@ -267,6 +267,16 @@ int build_plan(const char* spec, int batch, int dtype, int bn_mode, Plan* plan) 
       wa.x = wa.dy = nullptr; wa.dw_canonical = nullptr;
       wa.n = batch; wa.hc = st.hc; wa.wc = st.wc; wa.cin = st.cin; wa.cout = st.cout; wa.k = st.k; wa.up = st.up;
       wa.dtype = dtype;
+      if (st.thin == 0) {
+        // split-K scratch of the forward conv and of the conv that yields the input gradient
+        ConvArgs ca;
+        ca.x = ca.w = nullptr; ca.bias = nullptr; ca.y = nullptr; ca.partial = nullptr; ca.y_aux = nullptr;
+        ca.n = batch; ca.hc = st.hc; ca.wc = st.wc; ca.cin = st.cin; ca.cout = st.cout; ca.k = st.k; ca.up = st.up;
+        ca.act = ACT_NONE; ca.dtype = dtype;
+        if (!st.has_bn) plan->max_wgrad_floats = std::max(plan->max_wgrad_floats, conv_mfma_splitk_floats(ca));
+        ca.cin = st.cout; ca.cout = st.cin; ca.up = 0;
+        plan->max_wgrad_floats = std::max(plan->max_wgrad_floats, conv_mfma_splitk_floats(ca));
+      }
       if (st.thin == 1) {
         plan->max_wgrad_floats = std::max(plan->max_wgrad_floats, thin_wgrad_workspace_floats(rows, st.cin, st.cout));
         if (thin_wgrad_mfma_supported(st.cin, st.cout, st.wc, dtype))
