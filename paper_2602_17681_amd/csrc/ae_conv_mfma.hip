@@ -791,7 +791,7 @@ static int conv_mfma_splits(const ConvArgs& a) {
   const IgemmTile t = pick_tile(M, a.cout, a.cin, es);
   const int64_t tiles = ((M + t.bm - 1) / t.bm) * ((a.cout + t.bn - 1) / t.bn);
   const int64_t KT = (int64_t)a.k * a.k * a.cin * es / t.bkb;
-  if (tiles >= 128 || KT < 16) return 1;
+  if (tiles >= 256 || KT < 16) return 1;          // one workgroup per compute unit or more: no split
   int64_t splits = (512 + tiles - 1) / tiles;
   if (splits > KT / 4) splits = KT / 4;
   return splits < 1 ? 1 : (int)splits;

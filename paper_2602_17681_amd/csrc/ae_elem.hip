@@ -75,34 +75,46 @@ __global__ void k_pack_weights(const float* __restrict__ w, T* __restrict__ wp, 
   }
 }
 
-// All layers of a pass in one launch: job j owns workgroups [first_block[j], first_block[j+1]),
-// 1024 packed elements per workgroup.
+// All layers of a pass in one launch: job j owns workgroups [first_block[j], first_block[j+1]).
+// Forward layout [co][tap][ci]: 256 (co, ci) pairs per workgroup, ci fastest across threads; a
+// thread reads the k*k contiguous taps of its pair and scatters them — loads and stores of a
+// wavefront are contiguous.  Input-gradient layout [ci][flipped tap][co]: a workgroup owns a
+// 32 x 32 tile of pairs, reads it with ci fastest, turns it in LDS and writes with co fastest.
 template <typename T>
 __global__ void k_pack_weights_batch(PackBatch pb) {
+  __shared__ float tile[32 * 33 * 9];
   int ji = 0;
   while (ji + 1 < pb.n && (int64_t)blockIdx.x >= pb.job[ji + 1].first_block) ++ji;
   const PackJob& J = pb.job[ji];
-  const int cout = J.cout, cin = J.cin, k = J.k;
-  const int64_t total = (int64_t)cout * cin * k * k;
-  const int64_t base = ((int64_t)blockIdx.x - J.first_block) * (NT * 4);
+  const int cout = J.cout, cin = J.cin, kk = J.k * J.k;
+  const int64_t lb = (int64_t)blockIdx.x - J.first_block;
   T* __restrict__ wp = (T*)J.wp;
-#pragma unroll
-  for (int u = 0; u < 4; ++u) {
-    const int64_t i = base + u * NT + threadIdx.x;   // index in the PACKED layout: the stores coalesce
-    if (i >= total) break;
-    int64_t src;
-    if (!J.dgrad) {
-      int ci = (int)(i % cin); int64_t t = i / cin;
-      int s_ = (int)(t % k); t /= k;
-      int r = (int)(t % k); int co = (int)(t / k);
-      src = (((int64_t)co * cin + ci) * k + r) * k + s_;
-    } else {
-      int co = (int)(i % cout); int64_t t = i / cout;
-      int s_ = (int)(t % k); t /= k;
-      int r = (int)(t % k); int ci = (int)(t / k);
-      src = (((int64_t)co * cin + ci) * k + (k - 1 - r)) * k + (k - 1 - s_);
+  if (!J.dgrad) {
+    const int64_t i = lb * NT + threadIdx.x;
+    if (i >= (int64_t)cout * cin) return;
+    const int ci = (int)(i % cin), co = (int)(i / cin);
+    const float* __restrict__ src = J.w + ((int64_t)co * cin + ci) * kk;
+    for (int t = 0; t < kk; ++t) Store<T>::st(wp + ((int64_t)co * kk + t) * cin + ci, src[t]);
+    return;
+  }
+  const int tiles_ci = (cin + 31) / 32;
+  const int co0 = (int)(lb / tiles_ci) * 32, ci0 = (int)(lb % tiles_ci) * 32;
+  for (int it = 0; it < 4; ++it) {
+    const int p = it * NT + threadIdx.x;
+    const int ci_l = p & 31, co_l = p >> 5;
+    if (co0 + co_l < cout && ci0 + ci_l < cin) {
+      const float* __restrict__ src = J.w + ((int64_t)(co0 + co_l) * cin + ci0 + ci_l) * kk;
+      for (int t = 0; t < kk; ++t) tile[(co_l * 33 + ci_l) * kk + t] = src[t];
     }
-    Store<T>::st(wp + i, J.w[src]);
+  }
+  __syncthreads();
+  for (int it = 0; it < 4; ++it) {
+    const int p = it * NT + threadIdx.x;
+    const int co_l = p & 31, ci_l = p >> 5;
+    if (co0 + co_l < cout && ci0 + ci_l < cin) {
+      for (int t = 0; t < kk; ++t)   // tap (r,s) -> (k-1-r, k-1-s)
+        Store<T>::st(wp + ((int64_t)(ci0 + ci_l) * kk + (kk - 1 - t)) * cout + co0 + co_l, tile[(co_l * 33 + ci_l) * kk + t]);
+    }
   }
 }
 
@@ -211,6 +223,7 @@ __device__ __forceinline__ void store_vec(T* p, const float (&v)[VEC]) {
   if (VEC == 1) Store<T>::st(p, v[0]);
   else Store<T>::stv(p, reinterpret_cast<const float(&)[Store<T>::VEC]>(v));
 }
+
 template <int VEC>
 __device__ __forceinline__ void load_f32(const float* p, float (&v)[VEC]) {
 #pragma unroll
@@ -665,8 +678,9 @@ int launch_pack_weights_batch(PackBatch& pb, int dtype, hipStream_t s) {
   int64_t blocks = 0;
   for (int j = 0; j < pb.n; ++j) {
     pb.job[j].first_block = blocks;
-    const int64_t total = (int64_t)pb.job[j].cout * pb.job[j].cin * pb.job[j].k * pb.job[j].k;
-    blocks += (total + NT * 4 - 1) / (NT * 4);
+    const int64_t pairs = (int64_t)pb.job[j].cout * pb.job[j].cin;
+    if (pb.job[j].k > 3) return fail(AE_EINVAL, "pack_weights: filters larger than 3x3 are not batched");
+    blocks += pb.job[j].dgrad ? (int64_t)((pb.job[j].cout + 31) / 32) * ((pb.job[j].cin + 31) / 32) : (pairs + NT - 1) / NT;
   }
   if (blocks > 0x7FFFFFFF) return fail(AE_EINVAL, "pack_weights: too many elements");
   DISPATCH_T(dtype, hipLaunchKernelGGL((k_pack_weights_batch<T>), dim3((unsigned)blocks), dim3(NT), 0, s, pb));
