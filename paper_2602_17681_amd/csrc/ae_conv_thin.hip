@@ -230,7 +230,11 @@ __global__ __launch_bounds__(NT) void k_thin_wgrad(const T* __restrict__ thin, c
   for (int64_t qc = q0; qc < q1; qc += CHUNK) {
     __syncthreads();
     // build G for pixels qc .. qc+CHUNK-1
-    for (int i = threadIdx.x; i < CHUNK * G; i += NT) {
+    // fixed trip count, unrolled: the loads of all passes are in flight together
+#pragma unroll
+    for (int k = 0; k < (CHUNK * G + NT - 1) / NT; ++k) {
+      const int i = threadIdx.x + k * NT;
+      if (i >= CHUNK * G) break;
       const int p = i / G, gi = i % G;
       const int ct = gi % CT, tap = gi / CT;
       const int r = tap / 3, s = tap % 3;
@@ -261,10 +265,19 @@ __global__ __launch_bounds__(NT) void k_thin_wgrad(const T* __restrict__ thin, c
       for (int i = threadIdx.x; i < CHUNK * (GP - G); i += NT) sg[i / (GP - G)][G + i % (GP - G)] = 0.0f;
     __syncthreads();
     if (cw < CW) {
-      for (int p = pl; p < CHUNK; p += lanes) {
+      // the wide values of all the thread's pixels first (lanes >= 4: at most 16 of them), then the sums
+      float wvs[16];
+#pragma unroll
+      for (int k = 0; k < 16; ++k) {
+        const int p = pl + k * lanes;
         const int64_t q = qc + p;
-        if (q >= q1) break;
-        const float wv = Store<T>::ld(wide + q * CW + cw);
+        wvs[k] = (p < CHUNK && q < q1) ? Store<T>::ld(wide + q * CW + cw) : 0.0f;
+      }
+#pragma unroll
+      for (int k = 0; k < 16; ++k) {
+        const int p = pl + k * lanes;
+        if (p >= CHUNK) break;
+        const float wv = wvs[k];
 #pragma unroll
         for (int i = 0; i < GP; i += 4) {
           const float4 g4 = *reinterpret_cast<const float4*>(&sg[p][i]);
