@@ -19,6 +19,10 @@ import workloads as wl
 
 PEAK = {"bf16": 2500.0, "f32": 157.3}     # dense MFMA TFLOP/s, MI355X
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch (fetched + written) of a kernel family, measured with rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE on this workload and scaled by the same counters of a plain 256 MiB copy (fetch x2.000,
+# write x1.000); commands and per-kernel table: profiles/cfg5_hbm_traffic.md.  Unmeasured: None.
+TRAFFIC_BYTES_PER_LAUNCH = {"cfg5": {"k_igemm": 83.4e6, "k_wgrad": 74.8e6}}
 
 
 def build_case(name, torch, ae, batch=None):
@@ -94,7 +98,7 @@ FAMILY = {"conv_mfma": "k_igemm", "dgrad_mfma": "k_igemm", "wgrad_mfma": "k_wgra
           "conv_thin_in_mfma": "k_thin_in_mfma", "dgrad_thin_mfma": "k_thin_in_mfma"}
 
 
-def roofline_of(rows, dtype):
+def roofline_of(rows, dtype, workload=None):
     """The kernel that takes the largest share of the step (all its launches together), priced
     against the roof that bounds it: total algorithmic FLOPs (or bytes) of its launches divided by
     their total HIP-event time, i.e. per-launch average work over per-launch average duration."""
@@ -114,10 +118,13 @@ def roofline_of(rows, dtype):
     if top["flops"] > 0 and top["flops"] / max(top["bytes"], 1.0) >= balance:
         ach = top["flops"] / top["ms"] / 1e9
         return dict(bound="mfma", kernel=name, achieved=ach, peak=PEAK[dtype], unit="TFLOP/s", frac=ach / PEAK[dtype],
-                    traffic=None, avg_ms=avg_ms, launches_per_step=top["launches"], flops_per_launch=top["flops"] / top["launches"])
+                    traffic=TRAFFIC_BYTES_PER_LAUNCH.get(workload, {}).get(name), avg_ms=avg_ms,
+                    launches_per_step=top["launches"], flops_per_launch=top["flops"] / top["launches"],
+                    bytes_per_launch=top["bytes"] / top["launches"])
     ach = top["bytes"] / top["ms"] / 1e6
     return dict(bound="hbm", kernel=name, achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS,
-                traffic=None, avg_ms=avg_ms, launches_per_step=top["launches"], bytes_per_launch=top["bytes"] / top["launches"])
+                traffic=TRAFFIC_BYTES_PER_LAUNCH.get(workload, {}).get(name), avg_ms=avg_ms,
+                launches_per_step=top["launches"], bytes_per_launch=top["bytes"] / top["launches"])
 
 
 def cpu_baseline(name, budget_s=20.0):
@@ -125,7 +132,7 @@ def cpu_baseline(name, budget_s=20.0):
     resolution, smaller batch), timed on this machine's host cores."""
     import oracle.ae_oracle as orc
     cfg = wl.CONFIGS[name]
-    sample = {"cfg1": 64, "cfg2": 8, "cfg3": 4, "cfg4": 4096, "cfg5": 1}[name]
+    sample = {"cfg1": 8192, "cfg2": 256, "cfg3": 16, "cfg4": 131072, "cfg5": 8}[name]   # 10-30 s of host work
     spec = cfg["spec"]
     bf = cfg["dtype"] == "bf16"
     params = wl.make_params(spec, cfg["seed"], bf16=bf)
@@ -211,7 +218,7 @@ def main():
         "dtype": cfg["dtype"], "data": "synthetic",
         "config": {"workload": "%s: %s" % (name, cfg["spec"]), "batch": st["B"], "snr_db": cfg["snr_db"],
                    "seed": cfg["seed"], "pass": "forward+loss+backward" if cfg["backward"] else "forward"},
-        "roofline": roofline_of(rows, cfg["dtype"]),
+        "roofline": roofline_of(rows, cfg["dtype"], name),
         "kernels": [dict(name=r["name"], ms_per_step=round(r["ms_per_step"], 5),
                          tflops=None if r["tflops"] is None else round(r["tflops"], 2),
                          gbs=None if r["gbs"] is None else round(r["gbs"], 1))
