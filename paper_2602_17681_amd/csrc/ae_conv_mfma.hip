@@ -8,11 +8,16 @@
 // BK contiguous channels of input pixel (h+r-p, w+s-p) (zero outside the image; read
 // through a x2 nearest upsample when `up`).  B is the packed weight [C_out][k][k][C_in].
 //
-// One workgroup of 256 threads (4 wavefronts, 2x2) computes a BM x BN tile with
-// v_mfma_f32_32x32x16_bf16 (bf16) or v_mfma_f32_32x32x2_f32 (fp32); A and B slabs are
-// staged through LDS, double buffered, one barrier per slab.  The epilogue adds the
-// bias, rounds to the storage type, optionally reduces per-channel sum / sum of squares
-// of the tile (batch-norm statistics), applies the activation and stores [M][N].
+// One workgroup of 256 threads (4 wavefronts) computes a BM x BN tile with
+// v_mfma_f32_32x32x16_bf16 (bf16) or v_mfma_f32_32x32x2_f32 (fp32).  Kernels in this file:
+//   k_conv3_patch  3x3 convolutions of 16/32/64-wide images: the input patch of a tile lives in LDS
+//                  and all nine taps are read from it (one global read per input element)
+//   k_igemm        every other shape: per-tap slabs through a three-stage global-to-LDS ring,
+//                  optionally split over K
+//   k_wgrad_row3   weight gradient, three taps per workgroup from one input patch (bf16)
+//   k_wgrad_rows, k_wgrad   weight gradient, one tap per workgroup (fp32, 1x1, odd shapes)
+// The shared epilogue adds the bias, rounds to the storage type, optionally reduces per-channel
+// sum / sum of squares of the tile (batch-norm statistics), applies the activation and stores [M][N].
 #include "ae_device.h"
 #include "ae_internal.h"
 
@@ -51,8 +56,7 @@ struct IgemmParams {
 // Global loads are buffer loads: the hardware range check returns zero for the offsets
 // that the loader marks invalid (zero padding of the image, rows past M or N), so no
 // select or clamp is needed, and addresses are 32-bit byte offsets that only change when
-// the filter tap changes.  Loads run two slabs ahead of the MFMAs through two register
-// sets; LDS is double buffered, one barrier per slab.
+// the filter tap changes.
 // ---------------------------------------------------------------------------
 typedef unsigned uint4v __attribute__((ext_vector_type(4)));
 typedef float float4v __attribute__((ext_vector_type(4)));

@@ -1,7 +1,8 @@
 // ae_conv_thin.hip — 3x3 convolutions with a "thin" side: the first layer (1..4
-// input channels) and the last layer (1..4 output channels) of the autoencoders.
-// With K = 9*C_in <= 36 or N = C_out <= 4 these layers are bound by HBM and by the
-// vector ALUs, not by the matrix cores, so they get their own kernels:
+// input channels) and the last layer (1..4 output channels) of the autoencoders, for
+// fp32 models and for the shapes the matrix-core versions (ae_conv_thin_mfma.hip) do not take.
+// With K = 9*C_in <= 36 or N = C_out <= 4 these layers are bound by HBM, not by the
+// matrix cores:
 //
 //   thin-in  conv : out[m][cw]  = b[cw] + sum_{ct,r,s} thin[n][ct][h+r-1][w+s-1] * Wk[cw][ct][r][s]
 //                   (forward of the first layer; input gradient of the last layer)
@@ -12,7 +13,8 @@
 //
 // The thin tensor is always planar [n][ct][H][W] — the layout of the library's
 // boundary — so the first / last layout change of the pipeline disappears into these
-// kernels; the wide tensor is [pixels][cw] like every other activation.
+// kernels; the wide tensor is [pixels][cw] like every other activation.  Also here: the
+// per-plane sums that give the bias gradient of the planar last layer.
 #include "ae_device.h"
 #include "ae_internal.h"
 
