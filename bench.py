@@ -167,6 +167,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-per-config", action="store_true")
     ap.add_argument("--kernels", action="store_true", help="also print the per-kernel table to stderr")
+    ap.add_argument("--no-overlap", action="store_true",
+                    help="keep every kernel of the backward pass on one stream (for per-kernel profiles: with the "
+                         "default two streams the weight-gradient kernels share the chip with other kernels)")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="only run a plain device-to-device copy of MIB MiB five times (reference for the "
                          "FETCH_SIZE / WRITE_SIZE counters of rocprofv3) and exit")
@@ -196,12 +199,15 @@ def main():
         args.no_cpu_baseline = True
     cfg = wl.CONFIGS[name]
     st = build_case(name, torch, ae)
+    if args.no_overlap:
+        st["m"].model_set_overlap(False)
     # timed region: exactly `steps` steps, no instrumentation
     dt = run_timed(st, ae, torch, args.steps, args.warmup, timing=False)
     value = st["B"] * args.steps / dt
     # the same `steps` steps again with a pair of HIP events around every launch, recorded on the
     # stream the kernels run on (the event records cost about 15 % of the step time, so the
-    # throughput above is measured without them): per-kernel durations for the roofline
+    # throughput above is measured without them): per-kernel durations for the roofline.  While timing is
+    # enabled the library keeps every kernel on this one stream, so each duration is one kernel's own.
     dt_events = run_timed(st, ae, torch, args.steps, 0, timing=True)
     rows = kernel_table(st, args.steps)
     if args.kernels:
@@ -217,7 +223,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg["dtype"], "data": "synthetic",
         "config": {"workload": "%s: %s" % (name, cfg["spec"]), "batch": st["B"], "snr_db": cfg["snr_db"],
-                   "seed": cfg["seed"], "pass": "forward+loss+backward" if cfg["backward"] else "forward"},
+                   "seed": cfg["seed"], "pass": "forward+loss+backward" if cfg["backward"] else "forward",
+                   "backward_streams": 1 if args.no_overlap else 2},
         "roofline": roofline_of(rows, cfg["dtype"], name),
         "kernels": [dict(name=r["name"], ms_per_step=round(r["ms_per_step"], 5),
                          tflops=None if r["tflops"] is None else round(r["tflops"], 2),

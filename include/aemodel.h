@@ -164,6 +164,14 @@ int model_get_activation(ae_model* m, int step, float* out_nchw, void* stream);
  * floating-point operations and bytes of one launch (2*M*N*K for the convolution
  * family; bytes every operand must cross HBM at least once).  name may be NULL. */
 int model_timing_enable(ae_model* m, int on);
+/* Scheduling of the backward pass (an execution detail, not part of the method).  By
+ * default (on = 1) model_backward enqueues the weight-gradient kernels on a second stream
+ * owned by the handle, ordered against the caller's stream by events in both directions:
+ * everything enqueued on the caller's stream after model_backward returns sees all
+ * gradients.  on = 0 keeps every kernel on the caller's stream in program order (also the
+ * behaviour while per-kernel timing is enabled, so that each measured duration belongs to
+ * one kernel alone).  Results are identical either way. */
+int model_set_overlap(ae_model* m, int on);
 int model_timing_slots(const ae_model* m, int* n_slots);
 int model_timing_read(ae_model* m, int slot, char* name, int name_len, double* total_ms, int64_t* launches,
                       double* flops_per_launch, double* bytes_per_launch);

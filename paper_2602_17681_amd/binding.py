@@ -22,7 +22,7 @@ SYMBOLS = [
     "model_describe", "model_create", "model_destroy", "model_param_count", "model_io_shape",
     "model_set_sample_offset", "model_forward", "model_backward", "model_loss_mse", "model_noise",
     "model_pnorm_awgn", "model_gen_bits", "model_count_errors", "model_num_steps", "model_step_info",
-    "model_get_activation", "model_timing_enable", "model_timing_slots", "model_timing_read", "model_timing_reset",
+    "model_get_activation", "model_timing_enable", "model_set_overlap", "model_timing_slots", "model_timing_read", "model_timing_reset",
     "model_last_error",
 ]
 
@@ -57,6 +57,7 @@ def _load():
     L.model_step_info.argtypes = [vp, C.c_int, C.POINTER(C.c_int), i64p]
     L.model_get_activation.argtypes = [vp, C.c_int, vp, vp]
     L.model_timing_enable.argtypes = [vp, C.c_int]
+    L.model_set_overlap.argtypes = [vp, C.c_int]
     L.model_timing_slots.argtypes = [vp, C.POINTER(C.c_int)]
     L.model_timing_read.argtypes = [vp, C.c_int, C.c_char_p, C.c_int, C.POINTER(C.c_double), i64p,
                                     C.POINTER(C.c_double), C.POINTER(C.c_double)]
@@ -156,6 +157,9 @@ class Model:
 
     def model_timing_enable(self, on):
         _check(lib.model_timing_enable(self._h, 1 if on else 0))
+
+    def model_set_overlap(self, on):
+        _check(lib.model_set_overlap(self._h, 1 if on else 0))
 
     def model_timing_reset(self):
         _check(lib.model_timing_reset(self._h))

@@ -15,6 +15,15 @@
 // Optional per-kernel timing: when enabled, every kernel launch of the executor is
 // bracketed by two HIP events on the caller's stream; model_timing_read turns the
 // pairs into accumulated milliseconds.  Slots are keyed by "<step>.<phase>.<kernel>".
+//
+// Backward pass, two streams.  The weight gradient of a layer is needed by nobody until the
+// pass ends, while the input gradient and the elementwise kernels of the next layer form the
+// critical path; the two kinds of work also want different resources (matrix cores vs. memory
+// bandwidth).  The weight-gradient kernels therefore run on a second ("side") stream of the
+// handle: forked by an event once the layer's conv-output gradient exists, joined by an event
+// before that gradient's buffer is written again (two such buffers alternate between layers)
+// and at the end of the pass.  With per-kernel timing enabled, or overlap switched off,
+// everything runs on the caller's stream in program order.
 struct TimeSlot {
   std::string name;
   double flops = 0.0, bytes = 0.0;  // algorithmic work of one launch
@@ -32,10 +41,18 @@ struct ae_model {
   char* ws = nullptr;
   void* grad_a = nullptr;
   void* grad_b = nullptr;
-  void* draw = nullptr;
+  void* draw = nullptr;            // the conv-output gradient buffer of the current layer ...
+  void* draw_buf[2] = {nullptr, nullptr};   // ... one of these two, alternating
+  int draw_sel = 0;
   void* dfull = nullptr;
   float* partial = nullptr;
-  float* wgrad_ws = nullptr;
+  float* wgrad_ws = nullptr;       // used on the side stream only (or on the caller's when not overlapping)
+  float* splitk_ws = nullptr;
+  bool overlap = true;
+  hipStream_t side = nullptr;
+  hipEvent_t ev_fork = nullptr;
+  hipEvent_t ev_wdone[2] = {nullptr, nullptr};   // weight gradient reading draw_buf[i] has finished
+  bool wpending[2] = {false, false};
   uint64_t first_sample = 0;
   bool have_forward = false;
   bool packed_in_batch = false;     // the current pass repacked all its weights with one launch
@@ -87,11 +104,32 @@ class TimedScope {
   hipEvent_t start_ = nullptr, stop_ = nullptr;
 };
 
-#define TIMED(step, tag, flops, bytes, call)                 \
-  do {                                                        \
-    TimedScope ts_(m, s, (step), (tag), (flops), (bytes));    \
-    AE_TRY(call);                                             \
+#define TIMED_ON(stream, step, tag, flops, bytes, call)            \
+  do {                                                              \
+    TimedScope ts_(m, (stream), (step), (tag), (flops), (bytes));   \
+    AE_TRY(call);                                                   \
   } while (0)
+#define TIMED(step, tag, flops, bytes, call) TIMED_ON(s, step, tag, flops, bytes, call)
+
+// Side stream of the backward pass: created on first use; null when the pass runs on one stream.
+hipStream_t side_stream(ae_model* m) {
+  if (!m->overlap || m->timing) return nullptr;
+  if (!m->side) {
+    if (hipStreamCreateWithFlags(&m->side, hipStreamNonBlocking) != hipSuccess) { m->side = nullptr; return nullptr; }
+    bool ok = hipEventCreateWithFlags(&m->ev_fork, hipEventDisableTiming) == hipSuccess;
+    for (int i = 0; i < 2 && ok; ++i) ok = hipEventCreateWithFlags(&m->ev_wdone[i], hipEventDisableTiming) == hipSuccess;
+    if (!ok) { m->overlap = false; return nullptr; }
+  }
+  return m->side;
+}
+// the caller's stream waits for the weight gradients still reading draw_buf[sel]
+int join_side(ae_model* m, int sel, hipStream_t s) {
+  if (m->wpending[sel]) {
+    AE_HIP(hipStreamWaitEvent(s, m->ev_wdone[sel], 0));
+    m->wpending[sel] = false;
+  }
+  return AE_OK;
+}
 
 int nblocks_for(int64_t rows) { return reduce_blocks(rows); }
 
@@ -172,8 +210,8 @@ int forward_conv(ae_model* m, int si, Step& st, const float* params, const void*
   a.dtype = P.dtype;
   a.partial = nullptr;
   a.y_aux = second_pass ? nullptr : st.aux;
-  a.splitk_ws = m->wgrad_ws;
-  a.splitk_floats = P.max_wgrad_floats;
+  a.splitk_ws = m->splitk_ws;
+  a.splitk_floats = P.max_splitk_floats;
   int nblk = 0;
   const double conv_flops = 2.0 * raw_el * st.cin * st.k * st.k;
   const double conv_bytes = (in_el + raw_el + wel) * es;
@@ -235,6 +273,13 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
   const double conv_flops = 2.0 * raw_el * st.cin * st.k * st.k;
   const void* dr = g;  // gradient w.r.t. the conv output (bias included)
   bool bias_done = st.has_bn;   // a batch-norm step gets its bias gradient from bn_bwd_finalize
+  if (st.has_bn || st.pool || st.act != ACT_NONE) {
+    // this layer's conv-output gradient goes to the other buffer than the previous layer's, and
+    // only after the weight gradient that read this buffer two layers ago has finished
+    m->draw_sel ^= 1;
+    m->draw = m->draw_buf[m->draw_sel];
+    AE_TRY(join_side(m, m->draw_sel, s));
+  }
   if (st.has_bn || st.pool) {
     if (st.has_bn) {
       const int64_t prow = (int64_t)P.batch * st.hout * st.wout;
@@ -262,6 +307,31 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
     TIMED(si, "bwd.bias_finalize", 0.0, 0.0,
           launch_colsum_finalize(m->partial, nblocks_for(rows), st.cout, grads + st.b_off, s));
   }
+  // Fork: the weight gradient reads dr and the saved input.  When dr is one of the two
+  // alternating buffers it may run beside the rest of the pass; a dr that is the incoming
+  // gradient itself is overwritten by the very next layer, so that case stays in order.
+  hipStream_t ws = s;
+  if (dr == m->draw) {
+    hipStream_t side = side_stream(m);
+    if (side) {
+      AE_HIP(hipEventRecord(m->ev_fork, s));
+      AE_HIP(hipStreamWaitEvent(side, m->ev_fork, 0));
+      ws = side;
+    }
+  }
+  if (ws == s) {
+    // in order on the caller's stream: the scratch buffer of the weight-gradient kernels is
+    // shared with those still running on the side stream
+    AE_TRY(join_side(m, 0, s));
+    AE_TRY(join_side(m, 1, s));
+  }
+  auto wgrad_enqueued = [&]() -> int {
+    if (ws != s) {
+      AE_HIP(hipEventRecord(m->ev_wdone[m->draw_sel], ws));
+      m->wpending[m->draw_sel] = true;
+    }
+    return AE_OK;
+  };
   if (st.thin == 2) {
     // dr is planar [n][C_out][H][W]
     TIMED(si, "bwd.bias_planesum", 0.0, raw_el * es,
@@ -269,13 +339,14 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
     TIMED(si, "bwd.bias_finalize", 0.0, 0.0,
           launch_colsum_finalize(m->partial, P.batch * plane_sums_split((int64_t)st.hc * st.wc), st.cout, grads + st.b_off, s));
     if (thin_wgrad_mfma_supported(st.cout, st.cin, st.win, P.dtype))
-      TIMED(si, "bwd.wgrad_thin_mfma", conv_flops, (in_el + raw_el) * es + wel * 4,
-            launch_thin_wgrad_mfma(dr, in, m->wgrad_ws, grads + st.w_off, P.batch, st.hin, st.win, st.cout, st.cin, 1,
-                                   st.up, s));
+      TIMED_ON(ws, si, "bwd.wgrad_thin_mfma", conv_flops, (in_el + raw_el) * es + wel * 4,
+               launch_thin_wgrad_mfma(dr, in, m->wgrad_ws, grads + st.w_off, P.batch, st.hin, st.win, st.cout, st.cin, 1,
+                                      st.up, ws));
     else
-      TIMED(si, "bwd.wgrad_thin", conv_flops, (in_el + raw_el) * es + wel * 4,
-            launch_thin_wgrad(dr, in, m->wgrad_ws, grads + st.w_off, P.batch, st.hin, st.win, st.cout, st.cin, 1, st.up,
-                              P.dtype, s));
+      TIMED_ON(ws, si, "bwd.wgrad_thin", conv_flops, (in_el + raw_el) * es + wel * 4,
+               launch_thin_wgrad(dr, in, m->wgrad_ws, grads + st.w_off, P.batch, st.hin, st.win, st.cout, st.cin, 1, st.up,
+                                 P.dtype, ws));
+    AE_TRY(wgrad_enqueued());
     if (st.needs_dx) {
       const double full_el = (double)rows * st.cin;
       if (thin_in_mfma_supported(st.cout, st.cin, st.k, 0, P.dtype)) {
@@ -302,12 +373,13 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
   }
   if (st.thin == 1) {
     if (thin_wgrad_mfma_supported(st.cin, st.cout, st.wc, P.dtype))
-      TIMED(si, "bwd.wgrad_thin_mfma", conv_flops, (in_el + raw_el) * es + wel * 4,
-            launch_thin_wgrad_mfma(in, dr, m->wgrad_ws, grads + st.w_off, P.batch, st.hc, st.wc, st.cin, st.cout, 0, 0, s));
+      TIMED_ON(ws, si, "bwd.wgrad_thin_mfma", conv_flops, (in_el + raw_el) * es + wel * 4,
+               launch_thin_wgrad_mfma(in, dr, m->wgrad_ws, grads + st.w_off, P.batch, st.hc, st.wc, st.cin, st.cout, 0, 0, ws));
     else
-      TIMED(si, "bwd.wgrad_thin", conv_flops, (in_el + raw_el) * es + wel * 4,
-            launch_thin_wgrad(in, dr, m->wgrad_ws, grads + st.w_off, P.batch, st.hc, st.wc, st.cin, st.cout, 0, 0,
-                              P.dtype, s));
+      TIMED_ON(ws, si, "bwd.wgrad_thin", conv_flops, (in_el + raw_el) * es + wel * 4,
+               launch_thin_wgrad(in, dr, m->wgrad_ws, grads + st.w_off, P.batch, st.hc, st.wc, st.cin, st.cout, 0, 0,
+                                 P.dtype, ws));
+    AE_TRY(wgrad_enqueued());
     return AE_OK;   // the first layer needs no input gradient
   }
   // weight gradient
@@ -316,11 +388,12 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
   wa.n = P.batch; wa.hc = st.hc; wa.wc = st.wc; wa.cin = st.cin; wa.cout = st.cout; wa.k = st.k; wa.up = st.up;
   wa.dtype = P.dtype;
   if (wgrad_mfma_supported(wa)) {
-    TIMED(si, "bwd.wgrad_mfma", conv_flops, (in_el + raw_el) * es + wel * 4, launch_wgrad_mfma(wa, m->wgrad_ws, s));
+    TIMED_ON(ws, si, "bwd.wgrad_mfma", conv_flops, (in_el + raw_el) * es + wel * 4, launch_wgrad_mfma(wa, m->wgrad_ws, ws));
   } else {
-    TIMED(si, "bwd.wgrad_zero", 0.0, wel * 4, launch_fill_zero(grads + st.w_off, (int64_t)wel * 4, s));
-    TIMED(si, "bwd.wgrad_direct", conv_flops, (in_el + raw_el) * es + wel * 4, launch_wgrad_direct(wa, s));
+    TIMED_ON(ws, si, "bwd.wgrad_zero", 0.0, wel * 4, launch_fill_zero(grads + st.w_off, (int64_t)wel * 4, ws));
+    TIMED_ON(ws, si, "bwd.wgrad_direct", conv_flops, (in_el + raw_el) * es + wel * 4, launch_wgrad_direct(wa, ws));
   }
+  AE_TRY(wgrad_enqueued());
   // input gradient: convolution of dr with the flipped, transposed weights at conv resolution
   if (st.needs_dx) {
     if (!m->packed_in_batch)
@@ -331,8 +404,8 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
     a.y = st.up ? m->dfull : gnext;
     a.n = P.batch; a.hc = st.hc; a.wc = st.wc; a.cin = st.cout; a.cout = st.cin; a.k = st.k; a.up = 0;
     a.act = ACT_NONE; a.dtype = P.dtype; a.partial = nullptr; a.y_aux = nullptr;
-    a.splitk_ws = m->wgrad_ws;                   // the weight gradient of this step is done with it
-    a.splitk_floats = P.max_wgrad_floats;
+    a.splitk_ws = m->splitk_ws;
+    a.splitk_floats = P.max_splitk_floats;
     const double full_el = (double)rows * st.cin;
     if (conv_mfma_supported(a))
       TIMED(si, "bwd.dgrad_mfma", conv_flops, (raw_el + full_el + wel) * es, launch_conv_mfma(a, s));
@@ -394,16 +467,26 @@ int model_create(const char* layer_spec, int batch, int dtype, int bn_mode, ae_m
   }
   m->grad_a = m->ws + P.off_grad_a;
   m->grad_b = m->ws + P.off_grad_b;
-  m->draw = m->ws + P.off_draw;
+  m->draw_buf[0] = m->ws + P.off_draw;
+  m->draw_buf[1] = m->ws + P.off_draw2;
+  m->draw = m->draw_buf[0];
   m->dfull = m->ws + P.off_dfull;
   m->partial = (float*)(m->ws + P.off_partial);
   m->wgrad_ws = (float*)(m->ws + P.off_wgrad);
+  m->splitk_ws = (float*)(m->ws + P.off_splitk);
   *out = m;
   return AE_OK;
 }
 
 void model_destroy(ae_model* m) {
   if (!m) return;
+  if (m->side) {
+    (void)hipStreamSynchronize(m->side);
+    (void)hipStreamDestroy(m->side);
+  }
+  if (m->ev_fork) (void)hipEventDestroy(m->ev_fork);
+  for (hipEvent_t e : m->ev_wdone)
+    if (e) (void)hipEventDestroy(e);
   if (m->ws) (void)hipFree(m->ws);
   for (TimeSlot& sl : m->slots)
     for (auto& pr : sl.pending) { (void)hipEventDestroy(pr.first); (void)hipEventDestroy(pr.second); }
@@ -414,6 +497,12 @@ void model_destroy(ae_model* m) {
 int model_timing_enable(ae_model* m, int on) {
   if (!m) return fail(AE_EINVAL, "model_timing_enable: null model");
   m->timing = on != 0;
+  return AE_OK;
+}
+
+int model_set_overlap(ae_model* m, int on) {
+  if (!m) return fail(AE_EINVAL, "model_set_overlap: null model");
+  m->overlap = on != 0;
   return AE_OK;
 }
 
@@ -532,6 +621,9 @@ int model_backward(ae_model* m, const void* params, const void* x, const void* d
   size_t first_param = ns;
   for (size_t i = 0; i < ns; ++i)
     if (P.steps[i].kind == ST_CONV) { first_param = i; break; }
+  // weight gradients a failed earlier call may have left on the side stream
+  AE_TRY(join_side(m, 0, s));
+  AE_TRY(join_side(m, 1, s));
   AE_TRY(pack_all(m, prm, true, s));
   for (size_t ii = ns; ii-- > first_param;) {
     Step& st = P.steps[ii];
@@ -556,6 +648,9 @@ int model_backward(ae_model* m, const void* params, const void* x, const void* d
         break;
     }
   }
+  // join: work enqueued on the caller's stream after this call sees every gradient
+  AE_TRY(join_side(m, 0, s));
+  AE_TRY(join_side(m, 1, s));
   return AE_OK;
 }
 

@@ -241,7 +241,7 @@ int build_plan(const char* spec, int batch, int dtype, int bn_mode, Plan* plan) 
     return at;
   };
   plan->max_act_elems = B * plan->c0 * plan->h0 * plan->w0;
-  plan->max_raw_elems = plan->max_full_elems = plan->max_partial_floats = plan->max_wgrad_floats = 0;
+  plan->max_raw_elems = plan->max_full_elems = plan->max_partial_floats = plan->max_wgrad_floats = plan->max_splitk_floats = 0;
   for (Step& st : plan->steps) {
     int64_t out_elems = B * st.cout * st.hout * st.wout;
     int64_t in_elems = B * st.cin * st.hin * st.win;
@@ -273,9 +273,9 @@ int build_plan(const char* spec, int batch, int dtype, int bn_mode, Plan* plan) 
         ca.x = ca.w = nullptr; ca.bias = nullptr; ca.y = nullptr; ca.partial = nullptr; ca.y_aux = nullptr;
         ca.n = batch; ca.hc = st.hc; ca.wc = st.wc; ca.cin = st.cin; ca.cout = st.cout; ca.k = st.k; ca.up = st.up;
         ca.act = ACT_NONE; ca.dtype = dtype;
-        if (!st.has_bn) plan->max_wgrad_floats = std::max(plan->max_wgrad_floats, conv_mfma_splitk_floats(ca));
+        if (!st.has_bn) plan->max_splitk_floats = std::max(plan->max_splitk_floats, conv_mfma_splitk_floats(ca));
         ca.cin = st.cout; ca.cout = st.cin; ca.up = 0;
-        plan->max_wgrad_floats = std::max(plan->max_wgrad_floats, conv_mfma_splitk_floats(ca));
+        plan->max_splitk_floats = std::max(plan->max_splitk_floats, conv_mfma_splitk_floats(ca));
       }
       if (st.thin == 1) {
         plan->max_wgrad_floats = std::max(plan->max_wgrad_floats, thin_wgrad_workspace_floats(rows, st.cin, st.cout));
@@ -299,10 +299,12 @@ int build_plan(const char* spec, int batch, int dtype, int bn_mode, Plan* plan) 
   }
   plan->off_grad_a = take(plan->max_act_elems * es);      // gradient ping-pong
   plan->off_grad_b = take(plan->max_act_elems * es);
-  plan->off_draw = take(plan->max_raw_elems * es);        // gradient at conv resolution
+  plan->off_draw = take(plan->max_raw_elems * es);        // gradient at conv resolution (two buffers: consecutive
+  plan->off_draw2 = take(plan->max_raw_elems * es);       // layers alternate, see the side stream of the backward pass)
   plan->off_dfull = take(plan->max_full_elems * es);      // input gradient before the 2x2 sum of an upsampled conv
   plan->off_partial = take(plan->max_partial_floats * 4);
   plan->off_wgrad = take(plan->max_wgrad_floats * 4);
+  plan->off_splitk = take(plan->max_splitk_floats * 4);
   plan->ws_bytes = total;
   return AE_OK;
 }

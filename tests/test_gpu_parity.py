@@ -237,6 +237,40 @@ def test_single_layers_bf16_gradients(ae, case):
     run_case(spec, batch, dtype="bf16", seed=300 + case, snr_db=10.0)
 
 
+# ------------------------------------------------------------------ backward pass on two streams
+@pytest.mark.parametrize("dtype,spec,batch", [
+    ("bf16", None, 8),                                                        # the largest configuration, scaled down
+    ("f32", "in:6x1x1,fc:64,relu,fc:32,pnorm,awgn,fc:64,relu,fc:6,sigmoid", 512),
+    # layers without activation run their weight gradient in order, between layers that use the second stream
+    ("bf16", "in:64x32x32,conv3:128,relu,conv3:64,conv3:128,relu,conv3:64,relu,conv3:64", 16),
+])
+def test_backward_two_streams_same_bits(ae, dtype, spec, batch):
+    """The weight gradients run on a second stream by default; with that switched off, and on
+    repeated calls, every gradient must come out bit for bit the same (the kernels are
+    deterministic, so any difference is a missing ordering between the two streams)."""
+    import torch
+    if spec is None:
+        spec = wl.scaled_spec("cfg5", 32)
+    bf = dtype == "bf16"
+    m = ae.Model(spec, batch, ae.DTYPES[dtype])
+    params = torch.from_numpy(wl.make_params(spec, 11, bf16=bf)).cuda()
+    x = torch.from_numpy(wl.make_input(spec, batch, 11, bf16=bf)).cuda().to(m.tdtype).contiguous()
+    y = torch.empty((batch,) + m.out_shape, dtype=m.tdtype, device="cuda")
+    dy = torch.from_numpy(wl.make_cotangent((batch,) + m.out_shape, 11, bf16=bf)).cuda().to(m.tdtype).contiguous()
+    got = []
+    for overlap in (False, True, True, False, True):
+        m.model_set_overlap(overlap)
+        g = torch.full((m.n_params,), float("nan"), dtype=torch.float32, device="cuda")
+        m.model_forward(params, x, 10.0, 11, y)
+        m.model_backward(params, x, dy, g)
+        # no synchronisation here: the copy below is enqueued on the same stream as the call
+        got.append(g.cpu().numpy())
+    m.close()
+    assert np.all(np.isfinite(got[0]))
+    for k in range(1, len(got)):
+        assert np.array_equal(got[0], got[k]), "call %d differs from the single-stream result" % k
+
+
 # ------------------------------------------------------------------ error handling (host side, no kernel faults)
 def test_error_codes(ae):
     import torch
@@ -305,8 +339,10 @@ def test_cfg5_full_resolution_backward_small_batch(ae):
 
 
 def test_cfg5_full_size_backward_properties(ae):
-    """Properties of the full-size cfg5 backward that hold at any size: run-to-run determinism,
-    exact linearity in dy for a power-of-two factor, zero bias gradient in front of batch-stat BN."""
+    """Properties of the full-size cfg5 backward that hold at any size: run-to-run determinism (the
+    first run keeps every kernel on one stream, the others use the second stream for the weight
+    gradients), exact linearity in dy for a power-of-two factor, zero bias gradient in front of
+    batch-stat BN."""
     import torch
     cfg = wl.CONFIGS["cfg5"]
     B = cfg["batch"]
@@ -317,7 +353,8 @@ def test_cfg5_full_size_backward_properties(ae):
     dy = torch.empty_like(y)
     loss = torch.zeros(1, device="cuda")
     grads = []
-    for scale in (1.0, 1.0, 4.0):
+    for k, scale in enumerate((1.0, 1.0, 4.0)):
+        m.model_set_overlap(k > 0)
         m.model_forward(p, x, 10.0, cfg["seed"], y)
         ae.model_loss_mse(y, x, loss, dy)
         g = torch.full((m.n_params,), float("nan"), device="cuda")
