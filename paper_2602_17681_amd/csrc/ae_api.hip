@@ -53,6 +53,8 @@ struct ae_model {
   hipEvent_t ev_fork = nullptr;
   hipEvent_t ev_wdone[2] = {nullptr, nullptr};   // weight gradient reading draw_buf[i] has finished
   bool wpending[2] = {false, false};
+  hipEvent_t ev_pack = nullptr;    // the weight repacking enqueued on the side stream has finished
+  bool pack_pending = false;
   uint64_t first_sample = 0;
   bool have_forward = false;
   bool packed_in_batch = false;     // the current pass repacked all its weights with one launch
@@ -118,6 +120,7 @@ hipStream_t side_stream(ae_model* m) {
     if (hipStreamCreateWithFlags(&m->side, hipStreamNonBlocking) != hipSuccess) { m->side = nullptr; return nullptr; }
     bool ok = hipEventCreateWithFlags(&m->ev_fork, hipEventDisableTiming) == hipSuccess;
     for (int i = 0; i < 2 && ok; ++i) ok = hipEventCreateWithFlags(&m->ev_wdone[i], hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&m->ev_pack, hipEventDisableTiming) == hipSuccess;
     if (!ok) { m->overlap = false; return nullptr; }
   }
   return m->side;
@@ -172,8 +175,31 @@ int pack_all(ae_model* m, const float* params, bool dgrad, hipStream_t s) {
   return AE_OK;
 }
 
+// The repacking of a pass's weights runs on the side stream, beside the first (thin) layer of
+// the pass, which has a packing kernel of its own: forked after everything the caller's stream
+// holds (the writers of params, the readers of the packed copies), joined before the first
+// kernel that reads a packed copy and, at the latest, at the end of the pass.
+int pack_all_beside(ae_model* m, const float* params, bool dgrad, hipStream_t s) {
+  hipStream_t side = side_stream(m);
+  if (!side) return pack_all(m, params, dgrad, s);
+  AE_HIP(hipEventRecord(m->ev_fork, s));
+  AE_HIP(hipStreamWaitEvent(side, m->ev_fork, 0));
+  AE_TRY(pack_all(m, params, dgrad, side));
+  AE_HIP(hipEventRecord(m->ev_pack, side));
+  m->pack_pending = true;
+  return AE_OK;
+}
+int join_pack(ae_model* m, hipStream_t s) {
+  if (m->pack_pending) {
+    AE_HIP(hipStreamWaitEvent(s, m->ev_pack, 0));
+    m->pack_pending = false;
+  }
+  return AE_OK;
+}
+
 int forward_conv(ae_model* m, int si, Step& st, const float* params, const void* in, hipStream_t s) {
   const Plan& P = m->plan;
+  if (st.thin == 0) AE_TRY(join_pack(m, s));
   const double es = (double)dtype_size(P.dtype);
   const int64_t rows = (int64_t)P.batch * st.hc * st.wc;
   const double wel = (double)st.cout * st.cin * st.k * st.k;
@@ -396,6 +422,7 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
   AE_TRY(wgrad_enqueued());
   // input gradient: convolution of dr with the flipped, transposed weights at conv resolution
   if (st.needs_dx) {
+    AE_TRY(join_pack(m, s));
     if (!m->packed_in_batch)
       TIMED(si, "bwd.pack_weights", 0.0, wel * (4.0 + es),
             launch_pack_weights(params + st.w_off, st.wpack_d, st.cout, st.cin, st.k, P.dtype, true, s));
@@ -485,6 +512,7 @@ void model_destroy(ae_model* m) {
     (void)hipStreamDestroy(m->side);
   }
   if (m->ev_fork) (void)hipEventDestroy(m->ev_fork);
+  if (m->ev_pack) (void)hipEventDestroy(m->ev_pack);
   for (hipEvent_t e : m->ev_wdone)
     if (e) (void)hipEventDestroy(e);
   if (m->ws) (void)hipFree(m->ws);
@@ -576,7 +604,8 @@ int model_forward(ae_model* m, const void* params, const void* x, float snr_db, 
   const float sigma = (float)pow(10.0, -(double)snr_db / 20.0);
   m->have_forward = false;
   const size_t ns = P.steps.size();
-  AE_TRY(pack_all(m, prm, false, s));
+  AE_TRY(join_pack(m, s));
+  AE_TRY(pack_all_beside(m, prm, false, s));
   for (size_t i = 0; i < ns; ++i) {
     Step& st = P.steps[i];
     const void* in = step_input(m, i, x);
@@ -603,6 +632,7 @@ int model_forward(ae_model* m, const void* params, const void* x, float snr_db, 
     size_t bytes = (size_t)P.batch * st.cout * st.hout * st.wout * dtype_size(P.dtype);
     AE_HIP(hipMemcpyAsync(y, st.out, bytes, hipMemcpyDeviceToDevice, s));
   }
+  AE_TRY(join_pack(m, s));
   m->have_forward = true;
   return AE_OK;
 }
@@ -624,7 +654,8 @@ int model_backward(ae_model* m, const void* params, const void* x, const void* d
   // weight gradients a failed earlier call may have left on the side stream
   AE_TRY(join_side(m, 0, s));
   AE_TRY(join_side(m, 1, s));
-  AE_TRY(pack_all(m, prm, true, s));
+  AE_TRY(join_pack(m, s));
+  AE_TRY(pack_all_beside(m, prm, true, s));
   for (size_t ii = ns; ii-- > first_param;) {
     Step& st = P.steps[ii];
     void* gnext = (g == m->grad_a) ? m->grad_b : m->grad_a;
@@ -651,6 +682,7 @@ int model_backward(ae_model* m, const void* params, const void* x, const void* d
   // join: work enqueued on the caller's stream after this call sees every gradient
   AE_TRY(join_side(m, 0, s));
   AE_TRY(join_side(m, 1, s));
+  AE_TRY(join_pack(m, s));
   return AE_OK;
 }
 
