@@ -156,6 +156,14 @@ int pack_all(ae_model* m, const float* params, bool dgrad, hipStream_t s) {
   for (const Step& st : P.steps) {
     const bool want = dgrad ? needs_dgrad_pack(st) : needs_fwd_pack(P, st);
     if (!want) continue;
+    if (dgrad ? st.up_dgrad : st.up_phases) {
+      // upsampled conv in its cheaper form: summed weights, a kernel of their own
+      TIMED(0, dgrad ? "bwd.pack_weights_up" : "fwd.pack_weights_up", 0.0,
+            (double)st.cout * st.cin * (36.0 + 16.0 * (double)dtype_size(P.dtype)),
+            launch_pack_weights_up(params + st.w_off, dgrad ? st.wpack_d : st.wpack, st.cout, st.cin, P.dtype,
+                                   dgrad ? CONV_UP_DGRAD : CONV_UP_PHASES, s));
+      continue;
+    }
     if (st.k == 1 && (int64_t)st.cout * st.cin >= (1 << 20)) {
       // big fully-connected layers: bandwidth-bound conversion / transpose kernels of their own
       TIMED(0, dgrad ? "bwd.pack_weights_fc" : "fwd.pack_weights_fc", 0.0,
@@ -222,9 +230,14 @@ int forward_conv(ae_model* m, int si, Step& st, const float* params, const void*
   } else if (st.k == 1 && P.dtype == AE_F32 && !st.mfma) {
     w = params + st.w_off;  // [C_out][C_in] is already the packed order (the MFMA loader wants a 16-byte aligned copy)
   } else {
-    if (!m->packed_in_batch)
-      TIMED(si, "fwd.pack_weights", 0.0, wel * (4.0 + es),
-            launch_pack_weights(params + st.w_off, st.wpack, st.cout, st.cin, st.k, P.dtype, false, s));
+    if (!m->packed_in_batch) {
+      if (st.up_phases)
+        TIMED(si, "fwd.pack_weights_up", 0.0, wel * 4.0 + 16.0 * st.cout * st.cin * es,
+              launch_pack_weights_up(params + st.w_off, st.wpack, st.cout, st.cin, P.dtype, CONV_UP_PHASES, s));
+      else
+        TIMED(si, "fwd.pack_weights", 0.0, wel * (4.0 + es),
+              launch_pack_weights(params + st.w_off, st.wpack, st.cout, st.cin, st.k, P.dtype, false, s));
+    }
     w = st.wpack;
   }
   const bool second_pass = st.has_bn || st.pool;
@@ -238,6 +251,7 @@ int forward_conv(ae_model* m, int si, Step& st, const float* params, const void*
   a.y_aux = second_pass ? nullptr : st.aux;
   a.splitk_ws = m->splitk_ws;
   a.splitk_floats = P.max_splitk_floats;
+  if (st.up_phases) a.geom = CONV_UP_PHASES;
   int nblk = 0;
   const double conv_flops = 2.0 * raw_el * st.cin * st.k * st.k;
   const double conv_bytes = (in_el + raw_el + wel) * es;
@@ -263,7 +277,8 @@ int forward_conv(ae_model* m, int si, Step& st, const float* params, const void*
       const int pr = conv_partial_rows(a, true);
       nblk = (int)((rows + pr - 1) / pr);
     }
-    TIMED(si, "fwd.conv_mfma", conv_flops, conv_bytes, launch_conv_mfma(a, s));
+    // (the four-phase form of an upsampled conv executes 4/9 of the plain form's multiply-adds)
+    TIMED(si, "fwd.conv_mfma", st.up_phases ? conv_flops * 4.0 / 9.0 : conv_flops, conv_bytes, launch_conv_mfma(a, s));
   } else {
     TIMED(si, "fwd.conv_direct", conv_flops, conv_bytes, launch_conv_direct(a, s));
   }
@@ -423,22 +438,30 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
   // input gradient: convolution of dr with the flipped, transposed weights at conv resolution
   if (st.needs_dx) {
     AE_TRY(join_pack(m, s));
-    if (!m->packed_in_batch)
-      TIMED(si, "bwd.pack_weights", 0.0, wel * (4.0 + es),
-            launch_pack_weights(params + st.w_off, st.wpack_d, st.cout, st.cin, st.k, P.dtype, true, s));
+    if (!m->packed_in_batch) {
+      if (st.up_dgrad)
+        TIMED(si, "bwd.pack_weights_up", 0.0, wel * 4.0 + 16.0 * st.cout * st.cin * es,
+              launch_pack_weights_up(params + st.w_off, st.wpack_d, st.cout, st.cin, P.dtype, CONV_UP_DGRAD, s));
+      else
+        TIMED(si, "bwd.pack_weights", 0.0, wel * (4.0 + es),
+              launch_pack_weights(params + st.w_off, st.wpack_d, st.cout, st.cin, st.k, P.dtype, true, s));
+    }
     ConvArgs a;
     a.x = dr; a.w = st.wpack_d; a.bias = nullptr;
-    a.y = st.up ? m->dfull : gnext;
+    a.y = (st.up && !st.up_dgrad) ? m->dfull : gnext;
+    if (st.up_dgrad) a.geom = CONV_UP_DGRAD;   // straight to the stored resolution: no full-size gradient, no 2x2 sum
     a.n = P.batch; a.hc = st.hc; a.wc = st.wc; a.cin = st.cout; a.cout = st.cin; a.k = st.k; a.up = 0;
     a.act = ACT_NONE; a.dtype = P.dtype; a.partial = nullptr; a.y_aux = nullptr;
     a.splitk_ws = m->splitk_ws;
     a.splitk_floats = P.max_splitk_floats;
     const double full_el = (double)rows * st.cin;
     if (conv_mfma_supported(a))
-      TIMED(si, "bwd.dgrad_mfma", conv_flops, (raw_el + full_el + wel) * es, launch_conv_mfma(a, s));
+      // (the 4x4 stride-2 form executes 4/9 of the plain form's multiply-adds and writes the stored resolution)
+      TIMED(si, "bwd.dgrad_mfma", st.up_dgrad ? conv_flops * 4.0 / 9.0 : conv_flops,
+            (raw_el + (st.up_dgrad ? in_el : full_el) + wel) * es, launch_conv_mfma(a, s));
     else
       TIMED(si, "bwd.dgrad_direct", conv_flops, (raw_el + full_el + wel) * es, launch_conv_direct(a, s));
-    if (st.up)
+    if (st.up && !st.up_dgrad)
       TIMED(si, "bwd.upsum", 0.0, (full_el + in_el) * es,
             launch_upsum(m->dfull, gnext, P.batch, st.hin, st.win, st.cin, P.dtype, s));
   }
@@ -490,6 +513,17 @@ int model_create(const char* layer_spec, int batch, int dtype, int bn_mode, ae_m
       a.n = P.batch; a.hc = st.hc; a.wc = st.wc; a.cin = st.cin; a.cout = st.cout; a.k = st.k; a.up = st.up;
       a.dtype = P.dtype;
       st.mfma = conv_mfma_supported(a);
+      if (st.mfma && st.thin == 0 && st.up && st.k == 3) {
+        // the cheaper forms of an upsampled conv, decided once (the weight packing depends on it)
+        ConvArgs f = a;
+        f.act = (st.has_bn || st.pool) ? ACT_NONE : st.act;
+        f.partial = (st.has_bn && P.bn_mode == 0) ? (float*)m->ws : nullptr;   // only null / non-null matters here
+        f.y_aux = (st.has_bn || st.pool) ? nullptr : st.aux;
+        st.up_phases = conv_up_phases_usable(f);
+        ConvArgs d = a;
+        d.cin = st.cout; d.cout = st.cin; d.up = 0; d.act = ACT_NONE;
+        st.up_dgrad = st.needs_dx && conv_up_dgrad_usable(d);
+      }
     }
   }
   m->grad_a = m->ws + P.off_grad_a;

@@ -40,7 +40,25 @@ struct IgemmParams {
   // k_splitk_finish sums the splits and applies bias / rounding / activation
   int tiles_mn, slabs_per_split;
   float* split_out;
+  // Source geometry.  GEMM row m is pixel (n, i, j) of an Hc x Wc grid; tap (r, s) of that row
+  // reads source position (i*stride + r - pad_h, j*stride + s - pad_w) of an Hv x Wv image
+  // (stored at (Hv>>up) x (Wv>>up): nearest-neighbour upsampling folded into the read), zero
+  // outside.  Plain convolution: Hv = Hc, Wv = Wc, stride 1, pad = (ksz-1)/2.
+  int Hv, Wv, stride, pad;
+  // phases = 4: the convolution behind a x2 upsample, written as four 2x2 convolutions of the
+  // stored input (one per output parity (a, b) = (phase>>1, phase&1), pads 1-a and 1-b, weights
+  // w + phase*N*K); row (n, i, j) of phase (a, b) is output pixel (2i+a, 2j+b) of a 2Hc x 2Wc image
+  int phases;
 };
+
+// output row (pixel index in y) of GEMM row m
+__device__ __forceinline__ int64_t igemm_out_row(const IgemmParams& p, int64_t m, int phase) {
+  if (p.phases == 1) return m;
+  const unsigned mu = (unsigned)m;
+  const unsigned j = mu % (unsigned)p.Wc, t = mu / (unsigned)p.Wc;
+  const unsigned i = t % (unsigned)p.Hc, n = t / (unsigned)p.Hc;
+  return ((int64_t)n * (2 * p.Hc) + 2 * i + (phase >> 1)) * (2 * p.Wc) + 2 * j + (phase & 1);
+}
 
 // ---------------------------------------------------------------------------
 // The kernel, for T = bf16 (v_mfma_f32_32x32x16_bf16) or T = float (v_mfma_f32_32x32x2_f32).
@@ -92,7 +110,8 @@ template <> __device__ __forceinline__ void mma_step<float>(const uint4v& a, con
 // row stores staged through this wave's LDS area.
 template <typename T, int MI, int NJ, int WN, int SW, bool STATS, bool RELU>
 __device__ __forceinline__ void igemm_store_interior(const floatx16 (&acc)[MI][NJ], const float (&bias)[NJ], T* stage,
-                                                     T* yrow, int N, int lane, float (&s1)[NJ], float (&s2)[NJ]) {
+                                                     T* yrow, int N, int lane, float (&s1)[NJ], float (&s2)[NJ],
+                                                     const IgemmParams& p, int64_t mrow0, int phase, T* ycol) {
   constexpr int ES = (int)sizeof(T);
   constexpr int EPC = 16 / ES;               // elements per 16-byte chunk
   constexpr int CPRO = WN / EPC;             // chunks per staged row
@@ -114,8 +133,9 @@ __device__ __forceinline__ void igemm_store_interior(const floatx16 (&acc)[MI][N
     for (int c = 0; c < (32 * CPRO) / 64; ++c) {
       const int idx = c * 64 + lane;
       const int lr = idx / CPRO, ch = idx % CPRO;
-      *reinterpret_cast<uint4v*>(yrow + (int64_t)(i * 32 + lr) * N + ch * EPC) =
-          *reinterpret_cast<const uint4v*>(&stage[lr * SW + ch * EPC]);
+      T* dst = p.phases == 1 ? yrow + (int64_t)(i * 32 + lr) * N + ch * EPC
+                             : ycol + igemm_out_row(p, mrow0 + i * 32 + lr, phase) * N + ch * EPC;
+      *reinterpret_cast<uint4v*>(dst) = *reinterpret_cast<const uint4v*>(&stage[lr * SW + ch * EPC]);
     }
   }
 }
@@ -127,7 +147,8 @@ __device__ __forceinline__ void igemm_store_interior(const floatx16 (&acc)[MI][N
 // whole row segments.  smem: at least 4*32*(WN + 16/sizeof(T))*sizeof(T) bytes; sRed: [WGM][2][BN].
 template <typename T, int BM, int BN, int WGM, int WGN, bool INTERIOR>
 __device__ __forceinline__ void igemm_epilogue(floatx16 (&acc)[BM / WGM / 32][BN / WGN / 32], const IgemmParams& p,
-                                               char* smem, float (*sRed)[2][BN], int64_t m0, int n0, int64_t tile_m) {
+                                               char* smem, float (*sRed)[2][BN], int64_t m0, int n0, int64_t tile_m,
+                                               int phase = 0) {
   constexpr int ES = (int)sizeof(T);
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int MI = WM / 32, NJ = WN / 32;
@@ -146,9 +167,11 @@ __device__ __forceinline__ void igemm_epilogue(floatx16 (&acc)[BM / WGM / 32][BN
 #pragma unroll
     for (int j = 0; j < NJ; ++j) bias[j] = p.bias ? p.bias[n0 + wn * WN + j * 32 + col_lane] : 0.0f;
     T* yrow = Y + (m0 + wm * WM) * p.N + n0 + wn * WN;
-    if (p.partial) igemm_store_interior<T, MI, NJ, WN, SW, true, false>(acc, bias, stage, yrow, p.N, lane, s1, s2);
-    else if (p.act == ACT_RELU) igemm_store_interior<T, MI, NJ, WN, SW, false, true>(acc, bias, stage, yrow, p.N, lane, s1, s2);
-    else igemm_store_interior<T, MI, NJ, WN, SW, false, false>(acc, bias, stage, yrow, p.N, lane, s1, s2);
+    T* ycol = Y + n0 + wn * WN;
+    const int64_t mrow0 = m0 + wm * WM;
+    if (p.partial) igemm_store_interior<T, MI, NJ, WN, SW, true, false>(acc, bias, stage, yrow, p.N, lane, s1, s2, p, mrow0, phase, ycol);
+    else if (p.act == ACT_RELU) igemm_store_interior<T, MI, NJ, WN, SW, false, true>(acc, bias, stage, yrow, p.N, lane, s1, s2, p, mrow0, phase, ycol);
+    else igemm_store_interior<T, MI, NJ, WN, SW, false, false>(acc, bias, stage, yrow, p.N, lane, s1, s2, p, mrow0, phase, ycol);
   } else {
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
@@ -320,15 +343,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
-  const int lb0 = xcd_logical_block((int)blockIdx.x, (int)gridDim.x);
+  int lb0 = xcd_logical_block((int)blockIdx.x, (int)gridDim.x);
+  int phase = 0;
+  if (p.phases == 4) { phase = lb0 & 3; lb0 >>= 2; }   // the four phases of a tile run side by side: they read the same input
   const int split = INTERIOR ? 0 : lb0 / p.tiles_mn;
   const int lb = INTERIOR ? lb0 : lb0 - split * p.tiles_mn;
   const int tile_n = lb % p.tiles_n;
   const int64_t tile_m = lb / p.tiles_n;
   const int64_t m0 = tile_m * BM;
   const int n0 = tile_n * BN;
-  const int pad = (p.ksz - 1) >> 1;
-  const int Hin = p.Hc >> p.up, Win = p.Wc >> p.up;
+  const int pad_h = p.pad - (phase >> 1), pad_w = p.pad - (phase & 1);
+  const int Hin = p.Hv >> p.up, Win = p.Wv >> p.up;
   const __amdgpu_buffer_rsrc_t rX = make_rsrc(p.x, p.x_bytes);
   const __amdgpu_buffer_rsrc_t rW = make_rsrc(p.w, p.w_bytes);
 
@@ -354,7 +379,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
 #pragma unroll
   for (int i = 0; i < B_CHUNKS; ++i) {
     const int row = n0 + lrow + i * RSTEP;
-    b_off[i] = row < p.N ? (unsigned)row * (unsigned)p.K * (unsigned)ES + (unsigned)gchunk * 16u : kOob;
+    b_off[i] = row < p.N ? (unsigned)(phase * p.N + row) * (unsigned)p.K * (unsigned)ES + (unsigned)gchunk * 16u : kOob;
   }
 
   const int kt0 = INTERIOR ? 0 : split * p.slabs_per_split;             // first K slab of this workgroup
@@ -364,8 +389,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   {                                                                                                          \
     const int r_ = rs / p.ksz, s_ = rs - r_ * p.ksz;                                                         \
     _Pragma("unroll") for (int i = 0; i < A_CHUNKS; ++i) {                                                   \
-      const int hh = a_h[i] + r_ - pad, ww = a_w[i] + s_ - pad;                                              \
-      const bool ok = a_img[i] != kOob && hh >= 0 && hh < p.Hc && ww >= 0 && ww < p.Wc;                      \
+      const int hh = a_h[i] * p.stride + r_ - pad_h, ww = a_w[i] * p.stride + s_ - pad_w;                    \
+      const bool ok = a_img[i] != kOob && hh >= 0 && hh < p.Hv && ww >= 0 && ww < p.Wv;                      \
       const unsigned pix = (unsigned)((hh >> p.up) * Win + (ww >> p.up));                                    \
       a_off[i] = ok ? a_img[i] + pix * (unsigned)p.Cin * (unsigned)ES + (unsigned)gchunk * 16u : kOob;       \
     }                                                                                                        \
@@ -498,7 +523,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
       return;
     }
   }
-  igemm_epilogue<T, BM, BN, WGM, WGN, INTERIOR>(acc, p, smem, sRed, m0, n0, tile_m);
+  igemm_epilogue<T, BM, BN, WGM, WGN, INTERIOR>(acc, p, smem, sRed, m0, n0, tile_m, phase);
 }
 
 // y = act(round(sum over splits of partial[split] + bias)) for split-K launches
@@ -757,12 +782,25 @@ IgemmTile pick_tile(int64_t M, int cout, int cin, int es) {
 
 }  // namespace
 
-bool conv_mfma_supported(const ConvArgs& a) {
+// The GEMM behind the two forms of an upsampled convolution: rows are pixels of the STORED
+// (half-size) grid, 2x2 taps per phase or 4x4 taps with stride 2.
+static ConvArgs conv_effective(const ConvArgs& a) {
+  ConvArgs e = a;
+  if (a.geom == CONV_PLAIN) return e;
+  e.hc = a.hc / 2; e.wc = a.wc / 2; e.up = 0;
+  e.k = a.geom == CONV_UP_PHASES ? 2 : 4;
+  e.geom = CONV_PLAIN;                      // (applying this twice must not halve twice)
+  return e;
+}
+
+bool conv_mfma_supported(const ConvArgs& a0) {
+  const ConvArgs a = conv_effective(a0);
   const int es = (int)dtype_size(a.dtype);
   if ((a.cin * es) % 64 != 0 || a.cout < 32) return false;
   const int64_t M = (int64_t)a.n * a.hc * a.wc;
-  const int64_t x_bytes = (int64_t)a.n * (a.hc >> a.up) * (a.wc >> a.up) * a.cin * es;
-  const int64_t w_bytes = (int64_t)a.cout * a.k * a.k * a.cin * es;
+  const int64_t x_bytes = a0.geom == CONV_UP_DGRAD ? (int64_t)a0.n * a0.hc * a0.wc * a.cin * es
+                                                   : (int64_t)a.n * (a.hc >> a.up) * (a.wc >> a.up) * a.cin * es;
+  const int64_t w_bytes = (int64_t)a.cout * a.k * a.k * a.cin * es * (a0.geom == CONV_UP_PHASES ? 4 : 1);
   if (x_bytes >= 0x7FFFFFFF || w_bytes >= 0x7FFFFFFF) return false;   // 32-bit buffer offsets
   return M * ((a.cout + 63) / 64) / 128 < 0x7FFFFFFF && M < 0x7FFFFFFF;
 }
@@ -771,7 +809,7 @@ bool conv_mfma_supported(const ConvArgs& a) {
 // tiles of 256/W rows divide the image height, with enough tiles to fill the chip, and whose
 // epilogue needs no run-time checks.
 static bool conv3_patch_usable(const ConvArgs& a) {
-  if (a.k != 3 || !conv_mfma_supported(a)) return false;
+  if (a.geom != CONV_PLAIN || a.k != 3 || !conv_mfma_supported(a)) return false;
   if (a.wc != 16 && a.wc != 32 && a.wc != 64) return false;   // W = 128 needs 96 KB of LDS: one workgroup per compute unit, slower
   const int th = 256 / a.wc;
   if (a.hc % th != 0 || a.cout % 64 != 0) return false;
@@ -788,8 +826,9 @@ int conv_partial_rows(const ConvArgs& a, bool mfma) {
 }
 
 // Split-K: layers with fewer than 128 output tiles (small batch x fully-connected) and a long K.
-static int conv_mfma_splits(const ConvArgs& a) {
-  if (a.partial || !conv_mfma_supported(a) || conv3_patch_usable(a)) return 1;
+static int conv_mfma_splits(const ConvArgs& a0) {
+  if (a0.partial || a0.geom == CONV_UP_PHASES || !conv_mfma_supported(a0) || conv3_patch_usable(a0)) return 1;
+  const ConvArgs a = conv_effective(a0);
   const int es = (int)dtype_size(a.dtype);
   const int64_t M = (int64_t)a.n * a.hc * a.wc;
   const IgemmTile t = pick_tile(M, a.cout, a.cin, es);
@@ -801,22 +840,55 @@ static int conv_mfma_splits(const ConvArgs& a) {
   return splits < 1 ? 1 : (int)splits;
 }
 
-int64_t conv_mfma_splitk_floats(const ConvArgs& a) {
-  const int splits = conv_mfma_splits(a);
+int64_t conv_mfma_splitk_floats(const ConvArgs& a0) {
+  const int splits = conv_mfma_splits(a0);
+  const ConvArgs a = conv_effective(a0);
   return splits > 1 ? (int64_t)splits * a.n * a.hc * a.wc * a.cout : 0;
 }
 
-int launch_conv_mfma(const ConvArgs& a, hipStream_t s) {
-  if (!conv_mfma_supported(a)) return fail(AE_EINVAL, "conv_mfma: shape not supported");
+// Four 2x2 phase convolutions: the kernel's epilogue without run-time checks only, and
+// enough workgroups without splitting K.
+bool conv_up_phases_usable(const ConvArgs& a0) {
+  if (a0.up != 1 || a0.k != 3 || (a0.hc & 1) || (a0.wc & 1)) return false;
+  ConvArgs a = a0;
+  a.geom = CONV_UP_PHASES;
+  if (!conv_mfma_supported(a)) return false;
+  if (a.partial || a.y_aux || a.act == ACT_SIGMOID) return false;
+  const ConvArgs e = conv_effective(a);
+  const int64_t M = (int64_t)e.n * e.hc * e.wc;
+  const IgemmTile t = pick_tile(M, e.cout, e.cin, (int)dtype_size(e.dtype));
+  if (M % t.bm != 0 || e.cout % t.bn != 0) return false;
+  return (M / t.bm) * (e.cout / t.bn) * 4 >= 256;
+}
+
+bool conv_up_dgrad_usable(const ConvArgs& a0) {
+  if (a0.k != 3 || a0.up != 0 || (a0.hc & 1) || (a0.wc & 1) || a0.partial || a0.y_aux || a0.bias || a0.act != ACT_NONE) return false;
+  ConvArgs a = a0;
+  a.geom = CONV_UP_DGRAD;
+  return conv_mfma_supported(a);
+}
+
+int launch_conv_mfma(const ConvArgs& a0, hipStream_t s) {
+  if (!conv_mfma_supported(a0)) return fail(AE_EINVAL, "conv_mfma: shape not supported");
+  if (a0.geom == CONV_UP_PHASES && !conv_up_phases_usable(a0)) return fail(AE_EINVAL, "conv_mfma: phase form not usable here");
+  const ConvArgs a = conv_effective(a0);
   const int es = (int)dtype_size(a.dtype);
   IgemmParams p;
   p.x = a.x; p.w = a.w; p.bias = a.bias; p.y = a.y; p.y_aux = a.y_aux; p.partial = a.partial;
   p.M = (int64_t)a.n * a.hc * a.wc;
   p.N = a.cout; p.K = a.k * a.k * a.cin;
   p.Hc = a.hc; p.Wc = a.wc; p.Cin = a.cin; p.ksz = a.k; p.up = a.up; p.act = a.act;
+  p.Hv = a.hc; p.Wv = a.wc; p.stride = 1; p.pad = (a.k - 1) >> 1; p.phases = 1;
   p.x_bytes = (unsigned)((int64_t)a.n * (a.hc >> a.up) * (a.wc >> a.up) * a.cin * es);
   p.w_bytes = (unsigned)((int64_t)a.cout * a.k * a.k * a.cin * es);
-  if (conv3_patch_usable(a)) {
+  if (a0.geom == CONV_UP_PHASES) {
+    p.pad = 1; p.phases = 4;
+    p.w_bytes *= 4u;
+  } else if (a0.geom == CONV_UP_DGRAD) {
+    p.Hv = a0.hc; p.Wv = a0.wc; p.stride = 2; p.pad = 1;
+    p.x_bytes = (unsigned)((int64_t)a0.n * a0.hc * a0.wc * a.cin * es);
+  }
+  if (conv3_patch_usable(a0)) {
     const int bn = a.cout % 128 == 0 ? 128 : 64;
     p.tiles_n = a.cout / bn;
     dim3 pgrid((unsigned)((p.M / 256) * p.tiles_n));
@@ -841,13 +913,13 @@ int launch_conv_mfma(const ConvArgs& a, hipStream_t s) {
   p.tiles_n = (a.cout + t.bn - 1) / t.bn;
   const int64_t tiles_m = (p.M + t.bm - 1) / t.bm;
   const int KT = (int)((int64_t)p.K * es / t.bkb);
-  int splits = conv_mfma_splits(a);
+  int splits = conv_mfma_splits(a0);
   if (splits > 1 && (!a.splitk_ws || (int64_t)splits * p.M * p.N > a.splitk_floats)) splits = 1;
   p.tiles_mn = (int)(tiles_m * p.tiles_n);
   p.slabs_per_split = (KT + splits - 1) / splits;
   splits = (KT + p.slabs_per_split - 1) / p.slabs_per_split;
   p.split_out = splits > 1 ? a.splitk_ws : nullptr;
-  dim3 grid((unsigned)(tiles_m * p.tiles_n * splits));
+  dim3 grid((unsigned)(tiles_m * p.tiles_n * splits * p.phases));
   const bool interior = splits == 1 && p.M % t.bm == 0 && p.N % t.bn == 0 && !a.y_aux && a.act != ACT_SIGMOID &&
                         !(a.partial && a.act != ACT_NONE);
 #define IGEMM_LAUNCH_K(T, BMV, BNV, GM, GN, KB)                                                        \

@@ -605,6 +605,65 @@ __global__ void k_mse(const T* __restrict__ y, const T* __restrict__ t, int64_t 
   if (threadIdx.x == 0) atomicAdd(loss, acc * inv_n);
 }
 
+// Summed weights of the two cheaper forms of a 3x3 convolution behind a x2 upsample.
+// Rows (or columns) r of the filter that read the same stored input row collapse:
+//   forward, output parity a:  input offset di = 0 gets rows {0} (a = 0) or {0,1} (a = 1),
+//                              di = 1 gets rows {1,2} (a = 0) or {2} (a = 1);
+//   input gradient, tap e = 0..3 (output row 2i + e - 1):  rows {2}, {1,2}, {0,1}, {0}.
+// One thread per (co, ci) pair reads the nine weights and writes all sixteen sums (added in
+// fp32 in ascending (r, s) order, then rounded once to the storage type).
+//   geom 1: wp[phase][co][di][dj][ci]      geom 2: wp[ci][e][f][co]
+template <typename T>
+__global__ void k_pack_weights_up(const float* __restrict__ w, T* __restrict__ wp, int cout, int cin, int geom) {
+  const int64_t total = (int64_t)cout * cin;
+  for (int64_t idx = (int64_t)blockIdx.x * NT + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * NT) {
+    int co, ci;
+    if (geom == 1) { ci = (int)(idx % cin); co = (int)(idx / cin); }
+    else { co = (int)(idx % cout); ci = (int)(idx / cout); }
+    float f[3][3];
+    const float* src = w + ((int64_t)co * cin + ci) * 9;
+#pragma unroll
+    for (int r = 0; r < 3; ++r)
+#pragma unroll
+      for (int q = 0; q < 3; ++q) f[r][q] = src[r * 3 + q];
+    if (geom == 1) {
+#pragma unroll
+      for (int ph = 0; ph < 4; ++ph) {
+        const int a = ph >> 1, b = ph & 1;
+#pragma unroll
+        for (int di = 0; di < 2; ++di)
+#pragma unroll
+          for (int dj = 0; dj < 2; ++dj) {
+            const int r0 = di == 0 ? 0 : (a == 0 ? 1 : 2), r1 = di == 0 ? (a == 0 ? 0 : 1) : 2;
+            const int s0 = dj == 0 ? 0 : (b == 0 ? 1 : 2), s1 = dj == 0 ? (b == 0 ? 0 : 1) : 2;
+            float t = 0.0f;
+#pragma unroll
+            for (int r = 0; r < 3; ++r)
+#pragma unroll
+              for (int q = 0; q < 3; ++q)
+                if (r >= r0 && r <= r1 && q >= s0 && q <= s1) t += f[r][q];
+            Store<T>::st(wp + ((((int64_t)ph * cout + co) * 2 + di) * 2 + dj) * cin + ci, t);
+          }
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int r0 = e == 0 ? 2 : (e == 1 ? 1 : 0), r1 = e == 0 ? 2 : (e == 1 ? 2 : (e == 2 ? 1 : 0));
+          const int s0 = g == 0 ? 2 : (g == 1 ? 1 : 0), s1 = g == 0 ? 2 : (g == 1 ? 2 : (g == 2 ? 1 : 0));
+          float t = 0.0f;
+#pragma unroll
+          for (int r = 0; r < 3; ++r)
+#pragma unroll
+            for (int q = 0; q < 3; ++q)
+              if (r >= r0 && r <= r1 && q >= s0 && q <= s1) t += f[r][q];
+          Store<T>::st(wp + (((int64_t)ci * 4 + e) * 4 + g) * cout + co, t);
+        }
+    }
+  }
+}
+
 }  // namespace
 
 // ===========================================================================
@@ -692,6 +751,14 @@ int launch_pack_weights(const float* w, void* wp, int cout, int cin, int k, int 
   DISPATCH_T(dtype, hipLaunchKernelGGL((k_pack_weights<T>), dim3(grid_for(total, NT, 4096)), dim3(NT), 0, s, w, (T*)wp,
                                        cout, cin, k, for_dgrad ? 1 : 0));
   return launch_status("pack_weights");
+}
+
+int launch_pack_weights_up(const float* w, void* wp, int cout, int cin, int dtype, int geom, hipStream_t s) {
+  if (geom != CONV_UP_PHASES && geom != CONV_UP_DGRAD) return fail(AE_EINVAL, "pack_weights_up: bad form");
+  const int64_t total = (int64_t)cout * cin;
+  DISPATCH_T(dtype, hipLaunchKernelGGL((k_pack_weights_up<T>), dim3(grid_for(total, NT, 4096)), dim3(NT), 0, s, w, (T*)wp,
+                                       cout, cin, geom));
+  return launch_status("pack_weights_up");
 }
 
 int launch_col_stats(const void* x, int64_t rows, int c, int dtype, float* partial, hipStream_t s) {

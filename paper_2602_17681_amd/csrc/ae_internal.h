@@ -67,6 +67,8 @@ struct Step {
   float* aux = nullptr;             // binary32 copy of a sigmoid output produced in the conv epilogue (bf16 models):
                                     // y*(1-y) from a bf16-rounded y loses all accuracy where the sigmoid saturates
   bool mfma = false;                // forward uses the MFMA implicit-GEMM kernel
+  bool up_phases = false;           // forward of an upsampled conv as four 2x2 phase convolutions (CONV_UP_PHASES)
+  bool up_dgrad = false;            // its input gradient as one 4x4 stride-2 convolution (CONV_UP_DGRAD)
   int thin = 0;                     // 1: thin-in kernels (input is the planar boundary tensor); 2: thin-out kernels
   bool out_planar = false;          // `out` is stored planar [n][C][H][W] (thin-out step)
 };
@@ -126,7 +128,22 @@ struct ConvArgs {
   float* y_aux;    // nullable: binary32 copy of y (after the activation)
   float* splitk_ws = nullptr;      // scratch for split-K partial tiles (conv_mfma_splitk_floats), nullable: no split-K
   int64_t splitk_floats = 0;
+  // A 3x3 convolution behind a x2 nearest-neighbour upsample (up = 1; hc, wc = its output size)
+  // only ever sees four distinct inputs per output, so both directions have a cheaper form
+  // (4/9 of the multiply-adds, exact in real arithmetic):
+  //   CONV_UP_PHASES  forward: four 2x2 convolutions of the stored input, one per output parity,
+  //                   with weights summed over the taps that read the same input
+  //                   (w = [4][cout][2][2][cin], pack_weights_up);
+  //   CONV_UP_DGRAD   input gradient: one 4x4 stride-2 convolution of the output gradient
+  //                   (x = dY [n][hc][wc][cin], y = dX [n][hc/2][wc/2][cout], w = [cout][4][4][cin]),
+  //                   which also replaces the 2x2 sum over each upsampled pixel.
+  int geom = 0;
 };
+enum { CONV_PLAIN = 0, CONV_UP_PHASES = 1, CONV_UP_DGRAD = 2 };
+bool conv_up_phases_usable(const ConvArgs& a);   // a: the plain description (geom ignored)
+bool conv_up_dgrad_usable(const ConvArgs& a);    // a: the plain description of the input-gradient conv at conv resolution
+// Summed weights of the two forms above from the canonical [cout][cin][3][3] fp32 weights.
+int launch_pack_weights_up(const float* w, void* wp, int cout, int cin, int dtype, int geom, hipStream_t s);
 int64_t conv_mfma_splitk_floats(const ConvArgs& a);   // 0: this layer runs without split-K
 int launch_conv_direct(const ConvArgs& a, hipStream_t s);
 bool conv_mfma_supported(const ConvArgs& a);

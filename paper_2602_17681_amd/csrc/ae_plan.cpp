@@ -256,9 +256,11 @@ int build_plan(const char* spec, int batch, int dtype, int bn_mode, Plan* plan) 
       plan->max_full_elems = std::max(plan->max_full_elems, rows * st.cin);
       int64_t wel = (int64_t)st.cout * st.cin * st.k * st.k;
       // thin layers keep their weights repacked as MFMA operand rows of the wide side
-      st.off_wpack = take(std::max(wel * es, st.thin == 1 ? thin_wfrag_bytes(st.cout)
-                                             : st.thin == 2 ? thin_out_wz_bytes(st.cout, st.cin) : (int64_t)0));
-      st.off_wpack_d = take(std::max(wel * es, st.thin == 2 ? thin_wfrag_bytes(st.cin) : (int64_t)0));
+      // (the summed-weight forms of an upsampled 3x3 conv hold 16 taps instead of 9)
+      const int64_t wpk = (st.up && st.k == 3 ? (int64_t)16 * st.cout * st.cin : wel) * es;
+      st.off_wpack = take(std::max(wpk, st.thin == 1 ? thin_wfrag_bytes(st.cout)
+                                        : st.thin == 2 ? thin_out_wz_bytes(st.cout, st.cin) : (int64_t)0));
+      st.off_wpack_d = take(std::max(wpk, st.thin == 2 ? thin_wfrag_bytes(st.cin) : (int64_t)0));
       if (st.has_bn) st.off_bn = take(6 * (int64_t)st.cout * 4);
       int64_t blocks = std::max<int64_t>((rows + 127) / 128, reduce_blocks(rows));  // finest partial-sum granularity
       if (st.thin == 1) blocks = std::max<int64_t>(blocks, thin_in_mfma_blocks(batch, st.hc, st.wc));
@@ -276,6 +278,10 @@ int build_plan(const char* spec, int batch, int dtype, int bn_mode, Plan* plan) 
         if (!st.has_bn) plan->max_splitk_floats = std::max(plan->max_splitk_floats, conv_mfma_splitk_floats(ca));
         ca.cin = st.cout; ca.cout = st.cin; ca.up = 0;
         plan->max_splitk_floats = std::max(plan->max_splitk_floats, conv_mfma_splitk_floats(ca));
+        if (st.up && conv_up_dgrad_usable(ca)) {
+          ca.geom = CONV_UP_DGRAD;
+          plan->max_splitk_floats = std::max(plan->max_splitk_floats, conv_mfma_splitk_floats(ca));
+        }
       }
       if (st.thin == 1) {
         plan->max_wgrad_floats = std::max(plan->max_wgrad_floats, thin_wgrad_workspace_floats(rows, st.cin, st.cout));
