@@ -2,6 +2,7 @@
 // executor that walks the plan and enqueues one kernel sequence per step.
 #include <math.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <map>

@@ -228,6 +228,12 @@ LAYERS_BF16 = [
     ("in:3x16x16,conv3:64,bn,relu,pool2", 4),
     ("in:64x8x8,up2,conv3:3,sigmoid", 4),
     ("in:64x6x10,conv3:128,relu,up2,conv3:64", 3),      # sides that are not powers of two, ragged tiles
+    # enough tiles for the four-phase form of the upsampled conv (and the 4x4 stride-2 form of its input gradient).
+    # No ReLU behind the upsampled conv: its summed weights are rounded to bf16 once more, which moves the stored
+    # bf16 outputs by an ulp here and there (2.5e-3 in relative L2, inside the 2e-2 bar), and a ReLU mask taken on
+    # them would then differ from the oracle's in ~0.2 % of the elements: sqrt(0.002) = 4 % in every gradient,
+    # whatever the kernels do (see DEEP_BF16_GRAD); without it the gradients test the two forms themselves.
+    ("in:64x16x16,conv3:64,relu,up2,conv3:64", 32),
 ]
 
 
