@@ -54,8 +54,9 @@ struct ae_model {
   hipEvent_t ev_fork = nullptr;
   hipEvent_t ev_wdone[2] = {nullptr, nullptr};   // weight gradient reading draw_buf[i] has finished
   bool wpending[2] = {false, false};
-  hipEvent_t ev_pack = nullptr;    // the weight repacking enqueued on the side stream has finished
-  bool pack_pending = false;
+  hipEvent_t ev_pack = nullptr;    // the weight repacking enqueued on the side stream has finished ...
+  hipEvent_t ev_pack_fc = nullptr; // ... and that of the big fully-connected layers, which comes last
+  bool pack_pending = false, pack_fc_pending = false;
   uint64_t first_sample = 0;
   bool have_forward = false;
   bool packed_in_batch = false;     // the current pass repacked all its weights with one launch
@@ -122,6 +123,7 @@ hipStream_t side_stream(ae_model* m) {
     bool ok = hipEventCreateWithFlags(&m->ev_fork, hipEventDisableTiming) == hipSuccess;
     for (int i = 0; i < 2 && ok; ++i) ok = hipEventCreateWithFlags(&m->ev_wdone[i], hipEventDisableTiming) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&m->ev_pack, hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&m->ev_pack_fc, hipEventDisableTiming) == hipSuccess;
     if (!ok) { m->overlap = false; return nullptr; }
   }
   return m->side;
@@ -148,15 +150,20 @@ bool needs_dgrad_pack(const Step& st) { return st.kind == ST_CONV && st.thin == 
 
 // Repack the weights of every layer of a pass with one launch (more layers than a batch
 // holds: the per-layer launches remain).
-int pack_all(ae_model* m, const float* params, bool dgrad, hipStream_t s) {
+bool is_big_fc(const Step& st) { return st.k == 1 && (int64_t)st.cout * st.cin >= (1 << 20); }
+
+// part 0: everything but the big fully-connected layers; part 1: those (they take long and are
+// needed late in the forward pass, so they go last and get an event of their own)
+int pack_all(ae_model* m, const float* params, bool dgrad, hipStream_t s, int part) {
   const Plan& P = m->plan;
   PackBatch pb;
   pb.n = 0;
   double bytes = 0.0;
-  m->packed_in_batch = false;
+  if (part == 0) m->packed_in_batch = false;
   for (const Step& st : P.steps) {
     const bool want = dgrad ? needs_dgrad_pack(st) : needs_fwd_pack(P, st);
     if (!want) continue;
+    if ((part == 1) != (is_big_fc(st) && !(dgrad ? st.up_dgrad : st.up_phases))) continue;
     if (dgrad ? st.up_dgrad : st.up_phases) {
       // upsampled conv in its cheaper form: summed weights, a kernel of their own
       TIMED(0, dgrad ? "bwd.pack_weights_up" : "fwd.pack_weights_up", 0.0,
@@ -165,7 +172,7 @@ int pack_all(ae_model* m, const float* params, bool dgrad, hipStream_t s) {
                                    dgrad ? CONV_UP_DGRAD : CONV_UP_PHASES, s));
       continue;
     }
-    if (st.k == 1 && (int64_t)st.cout * st.cin >= (1 << 20)) {
+    if (is_big_fc(st)) {
       // big fully-connected layers: bandwidth-bound conversion / transpose kernels of their own
       TIMED(0, dgrad ? "bwd.pack_weights_fc" : "fwd.pack_weights_fc", 0.0,
             (double)st.cout * st.cin * (4.0 + (double)dtype_size(P.dtype)),
@@ -180,7 +187,7 @@ int pack_all(ae_model* m, const float* params, bool dgrad, hipStream_t s) {
   }
   if (pb.n > 0)
     TIMED(0, dgrad ? "bwd.pack_weights_all" : "fwd.pack_weights_all", 0.0, bytes, launch_pack_weights_batch(pb, P.dtype, s));
-  m->packed_in_batch = true;
+  if (part == 0) m->packed_in_batch = true;
   return AE_OK;
 }
 
@@ -190,25 +197,36 @@ int pack_all(ae_model* m, const float* params, bool dgrad, hipStream_t s) {
 // kernel that reads a packed copy and, at the latest, at the end of the pass.
 int pack_all_beside(ae_model* m, const float* params, bool dgrad, hipStream_t s) {
   hipStream_t side = side_stream(m);
-  if (!side) return pack_all(m, params, dgrad, s);
+  if (!side) {
+    AE_TRY(pack_all(m, params, dgrad, s, 0));
+    return pack_all(m, params, dgrad, s, 1);
+  }
   AE_HIP(hipEventRecord(m->ev_fork, s));
   AE_HIP(hipStreamWaitEvent(side, m->ev_fork, 0));
-  AE_TRY(pack_all(m, params, dgrad, side));
+  AE_TRY(pack_all(m, params, dgrad, side, 0));
   AE_HIP(hipEventRecord(m->ev_pack, side));
   m->pack_pending = true;
+  AE_TRY(pack_all(m, params, dgrad, side, 1));
+  AE_HIP(hipEventRecord(m->ev_pack_fc, side));
+  m->pack_fc_pending = true;
   return AE_OK;
 }
-int join_pack(ae_model* m, hipStream_t s) {
+// before the first kernel that reads a packed copy (big_fc: that of a big fully-connected layer)
+int join_pack(ae_model* m, hipStream_t s, bool big_fc = false) {
   if (m->pack_pending) {
     AE_HIP(hipStreamWaitEvent(s, m->ev_pack, 0));
     m->pack_pending = false;
+  }
+  if (big_fc && m->pack_fc_pending) {
+    AE_HIP(hipStreamWaitEvent(s, m->ev_pack_fc, 0));
+    m->pack_fc_pending = false;
   }
   return AE_OK;
 }
 
 int forward_conv(ae_model* m, int si, Step& st, const float* params, const void* in, hipStream_t s) {
   const Plan& P = m->plan;
-  if (st.thin == 0) AE_TRY(join_pack(m, s));
+  if (st.thin == 0) AE_TRY(join_pack(m, s, is_big_fc(st)));
   const double es = (double)dtype_size(P.dtype);
   const int64_t rows = (int64_t)P.batch * st.hc * st.wc;
   const double wel = (double)st.cout * st.cin * st.k * st.k;
@@ -438,7 +456,7 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
   AE_TRY(wgrad_enqueued());
   // input gradient: convolution of dr with the flipped, transposed weights at conv resolution
   if (st.needs_dx) {
-    AE_TRY(join_pack(m, s));
+    AE_TRY(join_pack(m, s, is_big_fc(st)));
     if (!m->packed_in_batch) {
       if (st.up_dgrad)
         TIMED(si, "bwd.pack_weights_up", 0.0, wel * 4.0 + 16.0 * st.cout * st.cin * es,
@@ -548,6 +566,7 @@ void model_destroy(ae_model* m) {
   }
   if (m->ev_fork) (void)hipEventDestroy(m->ev_fork);
   if (m->ev_pack) (void)hipEventDestroy(m->ev_pack);
+  if (m->ev_pack_fc) (void)hipEventDestroy(m->ev_pack_fc);
   for (hipEvent_t e : m->ev_wdone)
     if (e) (void)hipEventDestroy(e);
   if (m->ws) (void)hipFree(m->ws);
@@ -639,7 +658,7 @@ int model_forward(ae_model* m, const void* params, const void* x, float snr_db, 
   const float sigma = (float)pow(10.0, -(double)snr_db / 20.0);
   m->have_forward = false;
   const size_t ns = P.steps.size();
-  AE_TRY(join_pack(m, s));
+  AE_TRY(join_pack(m, s, true));
   AE_TRY(pack_all_beside(m, prm, false, s));
   for (size_t i = 0; i < ns; ++i) {
     Step& st = P.steps[i];
@@ -667,7 +686,7 @@ int model_forward(ae_model* m, const void* params, const void* x, float snr_db, 
     size_t bytes = (size_t)P.batch * st.cout * st.hout * st.wout * dtype_size(P.dtype);
     AE_HIP(hipMemcpyAsync(y, st.out, bytes, hipMemcpyDeviceToDevice, s));
   }
-  AE_TRY(join_pack(m, s));
+  AE_TRY(join_pack(m, s, true));
   m->have_forward = true;
   return AE_OK;
 }
@@ -689,7 +708,7 @@ int model_backward(ae_model* m, const void* params, const void* x, const void* d
   // weight gradients a failed earlier call may have left on the side stream
   AE_TRY(join_side(m, 0, s));
   AE_TRY(join_side(m, 1, s));
-  AE_TRY(join_pack(m, s));
+  AE_TRY(join_pack(m, s, true));
   AE_TRY(pack_all_beside(m, prm, true, s));
   for (size_t ii = ns; ii-- > first_param;) {
     Step& st = P.steps[ii];
@@ -717,7 +736,7 @@ int model_backward(ae_model* m, const void* params, const void* x, const void* d
   // join: work enqueued on the caller's stream after this call sees every gradient
   AE_TRY(join_side(m, 0, s));
   AE_TRY(join_side(m, 1, s));
-  AE_TRY(join_pack(m, s));
+  AE_TRY(join_pack(m, s, true));
   return AE_OK;
 }
 
