@@ -315,6 +315,9 @@ FULL_SIZE_LINEAR = [
     ("in:64x32x32,up2,conv3:64,conv1:32", 8, "f32"),
     ("in:64x128x128,conv3:64,conv3:128", 8, "bf16"),
     ("in:128x64x64,conv3:128,up2,conv3:64", 8, "bf16"),
+    # both forms of an upsampled conv at a size where the forward takes the four-phase form without
+    # split-K (4 phases x 128 tiles) and the input gradient runs as one launch of 256 tiles
+    ("in:64x32x32,conv3:256,up2,conv3:64", 32, "bf16"),
 ]
 
 
