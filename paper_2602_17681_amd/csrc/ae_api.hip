@@ -296,8 +296,9 @@ int forward_conv(ae_model* m, int si, Step& st, const float* params, const void*
       const int pr = conv_partial_rows(a, true);
       nblk = (int)((rows + pr - 1) / pr);
     }
-    // (the four-phase form of an upsampled conv executes 4/9 of the plain form's multiply-adds)
-    TIMED(si, "fwd.conv_mfma", st.up_phases ? conv_flops * 4.0 / 9.0 : conv_flops, conv_bytes, launch_conv_mfma(a, s));
+    // (slot FLOPs are the algorithmic ones of the definition; the four-phase form of an upsampled conv,
+    // named apart, executes 4/9 of them)
+    TIMED(si, st.up_phases ? "fwd.conv_mfma_phases" : "fwd.conv_mfma", conv_flops, conv_bytes, launch_conv_mfma(a, s));
   } else {
     TIMED(si, "fwd.conv_direct", conv_flops, conv_bytes, launch_conv_direct(a, s));
   }
@@ -475,8 +476,8 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
     a.splitk_floats = P.max_splitk_floats;
     const double full_el = (double)rows * st.cin;
     if (conv_mfma_supported(a))
-      // (the 4x4 stride-2 form executes 4/9 of the plain form's multiply-adds and writes the stored resolution)
-      TIMED(si, "bwd.dgrad_mfma", st.up_dgrad ? conv_flops * 4.0 / 9.0 : conv_flops,
+      // (the 4x4 stride-2 form, named apart, executes 4/9 of the algorithmic multiply-adds and writes the stored resolution)
+      TIMED(si, st.up_dgrad ? "bwd.dgrad_mfma_stride2" : "bwd.dgrad_mfma", conv_flops,
             (raw_el + (st.up_dgrad ? in_el : full_el) + wel) * es, launch_conv_mfma(a, s));
     else
       TIMED(si, "bwd.dgrad_direct", conv_flops, (raw_el + full_el + wel) * es, launch_conv_direct(a, s));
