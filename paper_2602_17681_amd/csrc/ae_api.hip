@@ -48,6 +48,7 @@ struct ae_model {
   void* dfull = nullptr;
   float* partial = nullptr;
   float* wgrad_ws = nullptr;       // used on the side stream only (or on the caller's when not overlapping)
+  float* wgrad_ws_inorder = nullptr;   // for the weight gradients that stay in order on the caller's stream
   float* splitk_ws = nullptr;
   bool overlap = true;
   hipStream_t side = nullptr;
@@ -380,9 +381,12 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
       ws = side;
     }
   }
-  if (ws == s) {
-    // in order on the caller's stream: the scratch buffer of the weight-gradient kernels is
-    // shared with those still running on the side stream
+  // Scratch of the weight-gradient kernels: a layer that stays in order because its conv-output
+  // gradient is the incoming buffer has scratch of its own, so that it need not wait for the
+  // side stream; any other launch on the caller's stream shares the side stream's scratch and
+  // waits for what is still running there.
+  float* const wws = (dr == m->draw || st.thin != 0) ? m->wgrad_ws : m->wgrad_ws_inorder;
+  if (ws == s && wws == m->wgrad_ws) {
     AE_TRY(join_side(m, 0, s));
     AE_TRY(join_side(m, 1, s));
   }
@@ -449,7 +453,7 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
   wa.n = P.batch; wa.hc = st.hc; wa.wc = st.wc; wa.cin = st.cin; wa.cout = st.cout; wa.k = st.k; wa.up = st.up;
   wa.dtype = P.dtype;
   if (wgrad_mfma_supported(wa)) {
-    TIMED_ON(ws, si, "bwd.wgrad_mfma", conv_flops, (in_el + raw_el) * es + wel * 4, launch_wgrad_mfma(wa, m->wgrad_ws, ws));
+    TIMED_ON(ws, si, "bwd.wgrad_mfma", conv_flops, (in_el + raw_el) * es + wel * 4, launch_wgrad_mfma(wa, wws, ws));
   } else {
     TIMED_ON(ws, si, "bwd.wgrad_zero", 0.0, wel * 4, launch_fill_zero(grads + st.w_off, (int64_t)wel * 4, ws));
     TIMED_ON(ws, si, "bwd.wgrad_direct", conv_flops, (in_el + raw_el) * es + wel * 4, launch_wgrad_direct(wa, ws));
@@ -554,6 +558,7 @@ int model_create(const char* layer_spec, int batch, int dtype, int bn_mode, ae_m
   m->dfull = m->ws + P.off_dfull;
   m->partial = (float*)(m->ws + P.off_partial);
   m->wgrad_ws = (float*)(m->ws + P.off_wgrad);
+  m->wgrad_ws_inorder = (float*)(m->ws + P.off_wgrad_inorder);
   m->splitk_ws = (float*)(m->ws + P.off_splitk);
   *out = m;
   return AE_OK;

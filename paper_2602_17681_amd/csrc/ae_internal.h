@@ -82,12 +82,13 @@ struct Plan {
   std::vector<Step> steps;
   // workspace sizing (bytes)
   int64_t ws_bytes = 0;
-  int64_t off_grad_a = 0, off_grad_b = 0, off_draw = 0, off_draw2 = 0, off_dfull = 0, off_partial = 0, off_wgrad = 0, off_splitk = 0;
+  int64_t off_grad_a = 0, off_grad_b = 0, off_draw = 0, off_draw2 = 0, off_dfull = 0, off_partial = 0, off_wgrad = 0, off_wgrad_inorder = 0, off_splitk = 0;
   int64_t max_act_elems = 0;        // largest step output
   int64_t max_raw_elems = 0;        // largest conv-resolution tensor (raw / dRaw)
   int64_t max_full_elems = 0;       // largest conv-resolution input gradient of an upsampled conv
   int64_t max_partial_floats = 0;   // column-reduction partial buffer
   int64_t max_wgrad_floats = 0;     // split partial tiles of the MFMA weight-gradient kernel
+  int64_t max_wgrad_inorder_floats = 0;   // the same for layers whose weight gradient runs in order on the caller's stream
   int64_t max_splitk_floats = 0;    // split-K partial tiles of the forward / input-gradient convolutions
 };
 

@@ -242,6 +242,7 @@ int build_plan(const char* spec, int batch, int dtype, int bn_mode, Plan* plan) 
   };
   plan->max_act_elems = B * plan->c0 * plan->h0 * plan->w0;
   plan->max_raw_elems = plan->max_full_elems = plan->max_partial_floats = plan->max_wgrad_floats = plan->max_splitk_floats = 0;
+  plan->max_wgrad_inorder_floats = 0;
   for (Step& st : plan->steps) {
     int64_t out_elems = B * st.cout * st.hout * st.wout;
     int64_t in_elems = B * st.cin * st.hin * st.win;
@@ -298,6 +299,10 @@ int build_plan(const char* spec, int batch, int dtype, int bn_mode, Plan* plan) 
       }
       else if (wgrad_mfma_supported(wa))
         plan->max_wgrad_floats = std::max(plan->max_wgrad_floats, wgrad_mfma_workspace_floats(wa));
+      // a layer without batch-norm, activation or pooling has no conv-output gradient buffer of its own: its
+      // weight gradient runs in order on the caller's stream, with scratch apart from the side stream's
+      if (!st.has_bn && !st.pool && st.act == ACT_NONE && st.thin == 0 && wgrad_mfma_supported(wa))
+        plan->max_wgrad_inorder_floats = std::max(plan->max_wgrad_inorder_floats, wgrad_mfma_workspace_floats(wa));
       if (st.thin == 2)
         plan->max_partial_floats = std::max(plan->max_partial_floats,
                                             B * plane_sums_split((int64_t)st.hc * st.wc) * 2 * (int64_t)st.cout);
@@ -310,6 +315,7 @@ int build_plan(const char* spec, int batch, int dtype, int bn_mode, Plan* plan) 
   plan->off_dfull = take(plan->max_full_elems * es);      // input gradient before the 2x2 sum of an upsampled conv
   plan->off_partial = take(plan->max_partial_floats * 4);
   plan->off_wgrad = take(plan->max_wgrad_floats * 4);
+  plan->off_wgrad_inorder = take(plan->max_wgrad_inorder_floats * 4);
   plan->off_splitk = take(plan->max_splitk_floats * 4);
   plan->ws_bytes = total;
   return AE_OK;
