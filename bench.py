@@ -183,6 +183,9 @@ def main():
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="only run a plain device-to-device copy of MIB MiB five times (reference for the "
                          "FETCH_SIZE / WRITE_SIZE counters of rocprofv3) and exit")
+    ap.add_argument("--channel-sweep", action="store_true",
+                    help="only time the stand-alone power-normalisation + noise kernel on 2^28 elements "
+                         "(latent lengths of the configurations) against the HBM roofline and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no sharding, no collectives): use --gpus 1")
@@ -199,6 +202,31 @@ def main():
         print(json.dumps({"copy_mib": args.calibrate_copy, "launches": 5}))
         return
     from paper_2602_17681_amd import binding as ae
+
+    if args.channel_sweep:
+        # the channel step moves 2 elements per latent element (read z, write y; the noise is generated, never
+        # read): inside the networks it handles 16 KB per sample, too little to show its bandwidth
+        rows = []
+        for dtype in (torch.float32, torch.bfloat16):
+            for n in (64, 128, 512, 1024, 4096):
+                batch = (1 << 28) // n
+                z = torch.randn(batch * n, device="cuda").to(dtype)
+                y = torch.empty_like(z)
+                for _ in range(3):
+                    ae.model_pnorm_awgn(z, y, batch, n, 10.0, 1, 0)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(10):
+                    ae.model_pnorm_awgn(z, y, batch, n, 10.0, 1, 0)
+                e1.record()
+                torch.cuda.synchronize()
+                ms = e0.elapsed_time(e1) / 10
+                gbs = 2.0 * batch * n * z.element_size() / ms / 1e6
+                rows.append(dict(dtype="bf16" if dtype == torch.bfloat16 else "f32", n=n, batch=batch, ms=round(ms, 4),
+                                 gbs=round(gbs, 1), frac_hbm_peak=round(gbs / HBM_PEAK_GBS, 3)))
+                del z, y
+        print(json.dumps({"kernel": "k_pnorm_awgn", "elements": 1 << 28, "peak_gbs": HBM_PEAK_GBS, "rows": rows}))
+        return
 
     name = args.config
     if args.spec:
