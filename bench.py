@@ -183,6 +183,8 @@ def main():
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="only run a plain device-to-device copy of MIB MiB five times (reference for the "
                          "FETCH_SIZE / WRITE_SIZE counters of rocprofv3) and exit")
+    ap.add_argument("--calibrate-mfma", action="store_true",
+                    help="only run the library's plain matrix-core loop (with and without LDS fragment reads) and exit")
     ap.add_argument("--channel-sweep", action="store_true",
                     help="only time the stand-alone power-normalisation + noise kernel on 2^28 elements "
                          "(latent lengths of the configurations) against the HBM roofline and exit")
@@ -203,6 +205,13 @@ def main():
         return
     from paper_2602_17681_amd import binding as ae
 
+    if args.calibrate_mfma:
+        plain = max(ae.model_calibrate_mfma(0) for _ in range(3))
+        with_lds = max(ae.model_calibrate_mfma(6) for _ in range(3))
+        print(json.dumps({"kernel": "k_calib_mfma", "nominal_peak_tflops": PEAK["bf16"], "mfma_only_tflops": round(plain, 1),
+                          "mfma_with_6_lds_reads_per_8_tflops": round(with_lds, 1),
+                          "frac_of_nominal": [round(plain / PEAK["bf16"], 3), round(with_lds / PEAK["bf16"], 3)]}))
+        return
     if args.channel_sweep:
         # the channel step moves 2 elements per latent element (read z, write y; the noise is generated, never
         # read): inside the networks it handles 16 KB per sample, too little to show its bandwidth

@@ -177,6 +177,14 @@ int model_timing_read(ae_model* m, int slot, char* name, int name_len, double* t
                       double* flops_per_launch, double* bytes_per_launch);
 int model_timing_reset(ae_model* m);
 
+/* Measurement aid: TFLOP/s of a loop of nothing but independent 32x32x16 bf16 matrix-core
+ * instructions on every compute unit (two workgroups of four wavefronts each), the practical
+ * ceiling beside the nominal peak; with lds_reads = 6 each wavefront also reads the six 16-byte
+ * fragments per lane that eight such instructions need in a 128x64 wave tile.  Synchronous:
+ * times `iters` iterations with HIP events on `stream` and waits.  scratch_dev: device memory
+ * of at least 1 KiB (never written in practice).  lds_reads is 0 or 6. */
+int model_calibrate_mfma(int lds_reads, int iters, float* scratch_dev, double* tflops, void* stream);
+
 const char* model_last_error(void);
 
 #ifdef __cplusplus

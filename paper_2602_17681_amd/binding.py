@@ -22,8 +22,8 @@ SYMBOLS = [
     "model_describe", "model_create", "model_destroy", "model_param_count", "model_io_shape",
     "model_set_sample_offset", "model_forward", "model_backward", "model_loss_mse", "model_noise",
     "model_pnorm_awgn", "model_gen_bits", "model_count_errors", "model_num_steps", "model_step_info",
-    "model_get_activation", "model_timing_enable", "model_set_overlap", "model_timing_slots", "model_timing_read", "model_timing_reset",
-    "model_last_error",
+    "model_get_activation", "model_timing_enable", "model_set_overlap", "model_calibrate_mfma", "model_timing_slots",
+    "model_timing_read", "model_timing_reset", "model_last_error",
 ]
 
 
@@ -58,6 +58,7 @@ def _load():
     L.model_get_activation.argtypes = [vp, C.c_int, vp, vp]
     L.model_timing_enable.argtypes = [vp, C.c_int]
     L.model_set_overlap.argtypes = [vp, C.c_int]
+    L.model_calibrate_mfma.argtypes = [C.c_int, C.c_int, vp, C.POINTER(C.c_double), vp]
     L.model_timing_slots.argtypes = [vp, C.POINTER(C.c_int)]
     L.model_timing_read.argtypes = [vp, C.c_int, C.c_char_p, C.c_int, C.POINTER(C.c_double), i64p,
                                     C.POINTER(C.c_double), C.POINTER(C.c_double)]
@@ -207,6 +208,13 @@ def model_pnorm_awgn(z, y, batch, n, snr_db, seed, first_sample):
     dtype = AE_BF16 if z.dtype == torch.bfloat16 else AE_F32
     assert z.numel() == batch * n and y.numel() == batch * n and y.dtype == z.dtype
     _check(lib.model_pnorm_awgn(_ptr(z), _ptr(y), batch, n, dtype, snr_db, seed, first_sample, _stream()))
+
+
+def model_calibrate_mfma(lds_reads, iters=4000):
+    scratch = torch.zeros(256, dtype=torch.float32, device="cuda")
+    out = C.c_double(0.0)
+    _check(lib.model_calibrate_mfma(lds_reads, iters, _ptr(scratch), C.byref(out), _stream()))
+    return out.value
 
 
 def model_gen_bits(seed, first_sample, batch, k, x_pm1):
