@@ -300,6 +300,21 @@ def test_error_codes(ae):
     assert "null" in ae.model_last_error()
 
 
+def test_calibration_loop_and_its_argument_checks(ae):
+    """The plain matrix-core loop (a measurement aid) runs, reports a rate in the range of the
+    hardware (above the fp32 vector peak, not above the datasheet's bf16 peak), and rejects bad arguments."""
+    import ctypes as C
+    import torch
+    plain = ae.model_calibrate_mfma(0, iters=500)
+    with_lds = ae.model_calibrate_mfma(6, iters=500)
+    assert 160.0 < with_lds <= plain * 1.05 and plain < 2500.0 * 1.02, (plain, with_lds)
+    out = C.c_double()
+    scratch = torch.zeros(256, device="cuda")
+    assert ae.lib.model_calibrate_mfma(3, 100, C.c_void_p(scratch.data_ptr()), C.byref(out), None) == -1
+    assert ae.lib.model_calibrate_mfma(0, 0, C.c_void_p(scratch.data_ptr()), C.byref(out), None) == -1
+    assert ae.lib.model_calibrate_mfma(0, 100, None, C.byref(out), None) == -1
+
+
 # ------------------------------------------------------------------ full benchmark sizes
 def test_cfg2_full_size_forward_backward(ae):
     """cfg2 exactly as bench.py runs it (batch 256, 3x32x32, fp32), every activation and gradient."""
