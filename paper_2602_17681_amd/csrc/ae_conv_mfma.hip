@@ -13,7 +13,9 @@
 //   k_conv3_patch  3x3 convolutions of 16/32/64-wide images: the input patch of a tile lives in LDS
 //                  and all nine taps are read from it (one global read per input element)
 //   k_igemm        every other shape: per-tap slabs through a three-stage global-to-LDS ring,
-//                  optionally split over K
+//                  optionally split over K; also the two cheaper forms of a 3x3 convolution behind
+//                  a x2 upsample (four 2x2 phase convolutions forward, one 4x4 stride-2
+//                  convolution for the input gradient; see IgemmParams)
 //   k_wgrad_row3   weight gradient, three taps per workgroup from one input patch (bf16)
 //   k_wgrad_rows, k_wgrad   weight gradient, one tap per workgroup (fp32, 1x1, odd shapes)
 // The shared epilogue adds the bias, rounds to the storage type, optionally reduces per-channel

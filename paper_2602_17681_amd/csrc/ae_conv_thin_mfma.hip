@@ -659,7 +659,15 @@ bool thin_wgrad_mfma_supported(int ct, int cw, int wq, int dtype) {
 
 int thin_wgrad_mfma_blocks(int n, int hq, int wq) {
   const int tiles = thin_tile(n, hq, wq).blocks;
-  return tiles < 768 ? tiles : 768;             // three persistent workgroups per compute unit
+  return tiles < 768 ? tiles : 768;             // upper bound of the persistent grid (sizes the partial buffer)
+}
+// Persistent workgroups actually launched: as many as are resident at once (registers allow
+// three per compute unit for 32 wide channels, two for 64, one beyond), so that every
+// workgroup walks the same number of patches and nobody waits for a second round.
+static int thin_wgrad_mfma_grid(int tiles, int cw) {
+  const int per_cu = cw <= 32 ? 3 : (cw <= 64 ? 2 : 1);
+  const int cap = 256 * per_cu;
+  return tiles < cap ? tiles : cap;
 }
 
 int64_t thin_wgrad_mfma_workspace_floats(int n, int hq, int wq, int cw) {
@@ -673,7 +681,7 @@ int launch_thin_wgrad_mfma(const void* thin, const void* wide, float* workspace,
   if (!thin_wgrad_mfma_supported(ct, cw, wq, AE_BF16) || up < 0 || up > 1 || (mode == 0 && up))
     return fail(AE_EINVAL, "thin_wgrad_mfma: shape not supported");
   const ThinTile t = thin_tile(n, hq, wq);
-  const int nblk = thin_wgrad_mfma_blocks(n, hq, wq);
+  const int nblk = thin_wgrad_mfma_grid(t.blocks, cw);
   const int vec = vec_ok(thin, wq << up) ? 1 : 0;
 #define LAUNCH_TWM(MIV)                                                                                         \
   hipLaunchKernelGGL((k_thin_wgrad_mfma<MIV>), dim3((unsigned)nblk), dim3(NT), 0, s, (const bf16_t*)thin,        \

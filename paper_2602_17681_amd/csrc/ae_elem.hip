@@ -874,7 +874,8 @@ int launch_fill_zero(void* p, int64_t bytes, hipStream_t s) {
 int launch_mse(const void* y, const void* t, int64_t n, int dtype, float* loss, void* dy, hipStream_t s) {
   AE_TRY(launch_fill_zero(loss, 4, s));
   const int vec = (((uintptr_t)y | (uintptr_t)t | (uintptr_t)dy) & 15) == 0 ? 1 : 0;
-  DISPATCH_T(dtype, hipLaunchKernelGGL((k_mse<T>), dim3(grid_for(n, NT * 16, 4096)), dim3(NT), 0, s, (const T*)y,
+  // at most 512 workgroups: each ends with one atomic add to the loss scalar, and same-address atomics serialise
+  DISPATCH_T(dtype, hipLaunchKernelGGL((k_mse<T>), dim3(grid_for(n, NT * 16, 512)), dim3(NT), 0, s, (const T*)y,
                                        (const T*)t, n, (float)(1.0 / (double)n), loss, (T*)dy, vec));
   return launch_status("mse");
 }
