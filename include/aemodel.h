@@ -177,6 +177,17 @@ int model_timing_read(ae_model* m, int slot, char* name, int name_len, double* t
                       double* flops_per_launch, double* bytes_per_launch);
 int model_timing_reset(ae_model* m);
 
+/* MX block quantisation Q(x) of the paper's Section "MX quantization", Eq. (1), applied to a
+ * row-major [rows][d] tensor (device memory, dtype AE_F32 or AE_BF16): every block of `block`
+ * consecutive elements of a row gets the power-of-two scale s = 2^(floor(log2 max|x_j|) - r_max)
+ * and every element becomes s * Q_e(x_j / s), Q_e being the FP4 E2M1 element quantiser (magnitudes
+ * 0, 0.5, 1, 1.5, 2, 3, 4, 6; r_max = 2; nearest value, ties to the even code, saturating at 6).
+ * An all-zero block yields zeros; the scale exponent is clamped to [-127, 127].  q has the shape
+ * and dtype of x and may be x itself.  d must be a positive multiple of block (32 in the paper's
+ * experiments); any block size works, sizes of 8 elements (bf16) / 4 (fp32) times a power of two
+ * up to 64 lanes, with 16-byte aligned pointers, take the vector path.  AE_EINVAL on bad arguments. */
+int model_mx_quantize(const void* x, void* q, int64_t rows, int64_t d, int block, int dtype, void* stream);
+
 /* Measurement aid: TFLOP/s of a loop of nothing but independent 32x32x16 bf16 matrix-core
  * instructions on every compute unit (two workgroups of four wavefronts each), the practical
  * ceiling beside the nominal peak; with lds_reads = 6 each wavefront also reads the six 16-byte

@@ -22,7 +22,7 @@ SYMBOLS = [
     "model_describe", "model_create", "model_destroy", "model_param_count", "model_io_shape",
     "model_set_sample_offset", "model_forward", "model_backward", "model_loss_mse", "model_noise",
     "model_pnorm_awgn", "model_gen_bits", "model_count_errors", "model_num_steps", "model_step_info",
-    "model_get_activation", "model_timing_enable", "model_set_overlap", "model_calibrate_mfma", "model_timing_slots",
+    "model_get_activation", "model_timing_enable", "model_set_overlap", "model_calibrate_mfma", "model_mx_quantize", "model_timing_slots",
     "model_timing_read", "model_timing_reset", "model_last_error",
 ]
 
@@ -59,6 +59,7 @@ def _load():
     L.model_timing_enable.argtypes = [vp, C.c_int]
     L.model_set_overlap.argtypes = [vp, C.c_int]
     L.model_calibrate_mfma.argtypes = [C.c_int, C.c_int, vp, C.POINTER(C.c_double), vp]
+    L.model_mx_quantize.argtypes = [vp, vp, C.c_int64, C.c_int64, C.c_int, C.c_int, vp]
     L.model_timing_slots.argtypes = [vp, C.POINTER(C.c_int)]
     L.model_timing_read.argtypes = [vp, C.c_int, C.c_char_p, C.c_int, C.POINTER(C.c_double), i64p,
                                     C.POINTER(C.c_double), C.POINTER(C.c_double)]
@@ -208,6 +209,12 @@ def model_pnorm_awgn(z, y, batch, n, snr_db, seed, first_sample):
     dtype = AE_BF16 if z.dtype == torch.bfloat16 else AE_F32
     assert z.numel() == batch * n and y.numel() == batch * n and y.dtype == z.dtype
     _check(lib.model_pnorm_awgn(_ptr(z), _ptr(y), batch, n, dtype, snr_db, seed, first_sample, _stream()))
+
+
+def model_mx_quantize(x, q, rows, d, block=32):
+    dtype = AE_BF16 if x.dtype == torch.bfloat16 else AE_F32
+    assert x.numel() == rows * d and q.numel() == rows * d and q.dtype == x.dtype
+    _check(lib.model_mx_quantize(_ptr(x), _ptr(q), rows, d, block, dtype, _stream()))
 
 
 def model_calibrate_mfma(lds_reads, iters=4000):

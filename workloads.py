@@ -174,3 +174,17 @@ def make_cotangent(shape, seed, bf16=False):
     rng = np.random.default_rng([seed, 0xC07A])
     g = rng.standard_normal(shape).astype(np.float32)
     return round_to_bf16(g) if bf16 else g
+
+
+def make_activations(rows, d, seed, bf16=False):
+    """Synthetic stand-in for transformer activations [tokens][d] (float32): Gaussian entries with a
+    log-normal scale per channel and per token and a few outlier channels two orders of magnitude
+    above the rest (the heavy tails that block-wise scaling has to cope with).  No arithmetic of
+    the quantiser lives here."""
+    rng = np.random.default_rng([seed, 0xAC71])
+    x = rng.standard_normal((rows, d), dtype=np.float32)
+    chan = np.exp(rng.standard_normal(d).astype(np.float32))
+    chan[rng.choice(d, size=max(1, d // 512), replace=False)] *= 100.0
+    tok = np.exp(0.5 * rng.standard_normal((rows, 1)).astype(np.float32))
+    x = x * chan[None, :] * tok
+    return round_to_bf16(x) if bf16 else x
