@@ -137,6 +137,59 @@ def roofline_of(rows, dtype, workload=None):
                 launches_per_step=top["launches"], bytes_per_launch=top["bytes"] / top["launches"])
 
 
+# measured HBM bytes per launch of k_mx_quantize on this workload (profiles/mx_quantize.md): FETCH_SIZE x2.000 + WRITE_SIZE
+MX_TRAFFIC_BYTES = {"bf16": 1.0738e9}
+
+
+def bench_mx_quant(torch, ae, args):
+    """One step = Q(x) of a [65 536][4 096] activation tensor resident in HBM (the shape of 32 sequences of 2 048
+    tokens of a 4 096-wide model; blocks of 32).  Algorithmic bytes: the tensor read once and written once."""
+    rows, d, block = 65536, 4096, 32
+    dtype = torch.bfloat16 if args.dtype == "bf16" else torch.float32
+    gen = torch.Generator(device="cuda").manual_seed(7)
+    x = torch.randn(rows, d, device="cuda", generator=gen) * torch.exp(torch.randn(1, d, device="cuda", generator=gen))
+    x[:, ::509] *= 100.0                                  # a few outlier channels
+    x = x.to(dtype).contiguous()
+    q = torch.empty_like(x)
+    for _ in range(args.warmup):
+        ae.model_mx_quantize(x, q, rows, d, block)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ae.model_mx_quantize(x, q, rows, d, block)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    # the kernel's own duration: HIP events on the stream it runs on
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        ae.model_mx_quantize(x, q, rows, d, block)
+    e1.record()
+    torch.cuda.synchronize()
+    avg_ms = e0.elapsed_time(e1) / args.steps
+    nbytes = 2.0 * rows * d * x.element_size()
+    ach = nbytes / avg_ms / 1e6
+    # oracle on a bounded sample of the same tensor
+    import oracle.mx_oracle as mxo
+    sample = 32768
+    xs = x[:sample].float().cpu().numpy().astype("float64")
+    c0 = time.perf_counter()
+    mxo.mx_quantize(xs, block)
+    ct = time.perf_counter() - c0
+    return {
+        "metric": "tokens/sec, MX block quantisation Q(x)", "value": rows * args.steps / dt, "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
+        "config": {"workload": "mx_quant: Q(x), FP4 E2M1 elements, block 32", "tokens": rows, "d": d, "block": block},
+        "roofline": {"bound": "hbm", "kernel": "k_mx_quantize", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": ach / HBM_PEAK_GBS, "traffic": MX_TRAFFIC_BYTES.get(args.dtype), "avg_ms": avg_ms,
+                     "launches_per_step": 1,
+                     "bytes_per_launch": nbytes},
+        "cpu_baseline": {"value": sample / ct, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+                         "sample": "%d tokens of the same tensor, %.1f s" % (sample, ct)},
+    }
+
+
 def cpu_baseline(name, budget_s=20.0):
     """The oracle as it stands, on a bounded sample of the same workload (same layer list and
     resolution, smaller batch), timed on this machine's host cores."""
@@ -183,6 +236,9 @@ def main():
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="only run a plain device-to-device copy of MIB MiB five times (reference for the "
                          "FETCH_SIZE / WRITE_SIZE counters of rocprofv3) and exit")
+    ap.add_argument("--mx-quant", action="store_true",
+                    help="benchmark the MX block quantiser Q(x) (blocks of 32, FP4 E2M1 elements) on 65 536 tokens x 4 096 "
+                         "channels of synthetic activations instead of a network: one JSON line with roofline and cpu_baseline")
     ap.add_argument("--calibrate-mfma", action="store_true",
                     help="only run the library's plain matrix-core loop (with and without LDS fragment reads) and exit")
     ap.add_argument("--channel-sweep", action="store_true",
@@ -205,6 +261,9 @@ def main():
         return
     from paper_2602_17681_amd import binding as ae
 
+    if args.mx_quant:
+        print(json.dumps(bench_mx_quant(torch, ae, args)))
+        return
     if args.calibrate_mfma:
         plain = max(ae.model_calibrate_mfma(0) for _ in range(3))
         with_lds = max(ae.model_calibrate_mfma(6) for _ in range(3))
