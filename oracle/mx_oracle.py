@@ -68,3 +68,38 @@ def block_scales(x, block=32):
     nz = amax > 0.0
     s[nz] = np.ldexp(1.0, block_scale_exponent(amax[nz]))
     return s.reshape(x.shape[0], -1)
+
+
+# ---------------------------------------------------------------------------------------------
+# Transformation mean squared error (the paper's Definition "Transformation Mean Squared Error",
+# Eq. (2), and the block-wise error of its numerical analysis):
+#   T(x) = A x + v,   T^-1(y) = A^-1 y - A^-1 v,
+#   E(T)     = 1/d * mean over tokens of || x - T^-1(Q(T(x))) ||^2,
+#   E_B^i(T) = 1/B * sum over the channels j of block i of (x - T^-1(Q(T(x))))_j^2, averaged over tokens.
+# The inverse is an input (the caller supplies A^-1; nothing here inverts a matrix).
+# Reading: T(x) is rounded to the tensor's storage type (bf16 or binary32) before it is
+# quantised, like every stored activation; everything else is float64.
+# ---------------------------------------------------------------------------------------------
+def _round_bf16(a):
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).reshape(np.shape(a)).astype(np.float64)
+
+
+def transform_mse(x, A, v, Ainv, block=32, storage="f64"):
+    """Returns (E, E_blocks[d / block], yq) for tokens x [n][d]; storage in {"f64", "f32", "bf16"}."""
+    x = np.asarray(x, dtype=np.float64)
+    A = np.asarray(A, dtype=np.float64)
+    Ainv = np.asarray(Ainv, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    n, d = x.shape
+    y = x @ A.T + v                                        # T(x), token by token
+    if storage == "bf16":
+        y = _round_bf16(y)
+    elif storage == "f32":
+        y = y.astype(np.float32).astype(np.float64)
+    yq = mx_quantize(y, block)
+    xhat = yq @ Ainv.T - Ainv @ v                          # T^-1(Q(T(x)))
+    err2 = (x - xhat) ** 2
+    e_blocks = err2.reshape(n, d // block, block).sum(axis=2).mean(axis=0) / block
+    return float(err2.sum() / (n * d)), e_blocks, yq

@@ -124,3 +124,74 @@ def test_scale_exponent_clamps_to_e8m0():
     assert mx.mx_quantize(x)[0, 0] == 0.0                    # 2^-140 / 2^-127 = 2^-13 rounds to zero
     x[0, 0] = 3.0e38                                         # floor(log2) = 127 -> exponent 125: inside the range
     assert mx.block_scales(x)[0, 0] == 2.0 ** 125
+
+
+# ------------------------------------------------------------------ transformation mean squared error (Eq. 2)
+def _hadamard(n):
+    h = np.array([[1.0]])
+    while h.shape[0] < n:
+        h = np.block([[h, h], [h, -h]])
+    return h / np.sqrt(n)
+
+
+def test_transform_mse_identity_is_plain_quantisation_error():
+    x = np.random.default_rng(5).standard_normal((64, 128)) * 3.0
+    e, eb, yq = mx.transform_mse(x, np.eye(128), np.zeros(128), np.eye(128))
+    q = mx.mx_quantize(x)
+    assert np.array_equal(yq, q)
+    assert np.isclose(e, ((x - q) ** 2).mean(), rtol=1e-14)
+    assert np.allclose(eb, ((x - q) ** 2).reshape(64, 4, 32).mean(axis=(0, 2)), rtol=1e-14)
+    assert np.isclose(eb.mean(), e, rtol=1e-14)                       # E is the average of the block errors
+
+
+def test_transform_mse_paper_example_blocks():
+    """[10, 1, .5, .5] with H_4 and B = 2 (the paper's example): the first block's error falls, the second's rises."""
+    x = np.array([[10.0, 1.0, 0.5, 0.5]])
+    h4 = _hadamard(4)
+    _, eb_id, _ = mx.transform_mse(x, np.eye(4), np.zeros(4), np.eye(4), block=2)
+    _, eb_h, yq = mx.transform_mse(x, h4, np.zeros(4), h4.T, block=2)
+    assert np.array_equal(yq, [[6.0, 4.0, 4.0, 4.0]])
+    # in the ROTATED coordinates the paper's statement holds block by block ...
+    y = x @ h4.T
+    ey = ((y - yq) ** 2).reshape(2, 2).sum(axis=1)
+    ex = ((x - mx.mx_quantize(x, 2)) ** 2).reshape(2, 2).sum(axis=1)
+    assert ey[0] < ex[0] and ey[1] > ex[1]
+    # ... and back in the original coordinates an orthogonal map keeps the total (by hand: 4 vs 0.25 + 1.25 = 1.5)
+    assert np.isclose(eb_id.sum() * 2, 4.0) and np.isclose(eb_h.sum() * 2, 1.5)
+
+
+def test_transform_mse_orthogonal_map_preserves_the_error_norm_and_the_bound_holds():
+    rng = np.random.default_rng(6)
+    d = 64
+    x = rng.standard_normal((256, d)) * np.exp(rng.standard_normal(d))
+    h = _hadamard(d)
+    e, _, yq = mx.transform_mse(x, h, np.zeros(d), h.T)
+    y = x @ h.T
+    assert np.isclose(e, ((y - yq) ** 2).mean(), rtol=1e-12)           # ||A^-1 r|| = ||r|| for orthogonal A
+    # general invertible A and a shift: x - T^-1(Q(T x)) = A^-1 (T x - Q(T x))  (first step of the bound's proof) ...
+    A = rng.standard_normal((d, d)) + 4.0 * np.eye(d)
+    v = rng.standard_normal(d)
+    Ainv = np.linalg.inv(A)
+    e, eb, yq = mx.transform_mse(x, A, v, Ainv)
+    y = x @ A.T + v
+    resid = (y - yq) @ Ainv.T
+    assert np.isclose(e, (resid ** 2).mean(), rtol=1e-9)
+    # ... hence E(T) <= ||A^-1||_sigma^2 / d * E||y - Q(y)||^2
+    assert e <= np.linalg.norm(Ainv, 2) ** 2 * ((y - yq) ** 2).mean() * (1 + 1e-12)
+    assert np.isclose(eb.mean(), e, rtol=1e-12)
+    # a shift that centres the transformed tokens changes nothing in the algebra: T^-1 undoes it
+    e0, _, _ = mx.transform_mse(x, np.eye(d), v, np.eye(d))
+    assert np.isclose(e0, (((x + v) - mx.mx_quantize(x + v)) ** 2).mean(), rtol=1e-12)
+
+
+def test_transform_mse_power_of_two_gain_is_free():
+    """Q commutes with powers of two, so T = 2^k A has the error of A exactly."""
+    rng = np.random.default_rng(7)
+    d = 64
+    x = rng.standard_normal((128, d))
+    A = rng.standard_normal((d, d)) + 3.0 * np.eye(d)
+    Ainv = np.linalg.inv(A)
+    v = rng.standard_normal(d)
+    e1, eb1, _ = mx.transform_mse(x, A, v, Ainv)
+    e2, eb2, _ = mx.transform_mse(x, 8.0 * A, 8.0 * v, Ainv / 8.0)
+    assert np.isclose(e1, e2, rtol=1e-12) and np.allclose(eb1, eb2, rtol=1e-12)
