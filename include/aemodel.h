@@ -188,6 +188,24 @@ int model_timing_reset(ae_model* m);
  * up to 64 lanes, with 16-byte aligned pointers, take the vector path.  AE_EINVAL on bad arguments. */
 int model_mx_quantize(const void* x, void* q, int64_t rows, int64_t d, int block, int dtype, void* stream);
 
+/* Transformation mean squared error of the paper (Definition "Transformation Mean Squared Error",
+ * Eq. 2, and the block-wise error E_B^i of its numerical analysis) for the affine map
+ * T(x) = A x + v over `rows` tokens x[rows][d] (device, row-major, dtype AE_F32 or AE_BF16):
+ *     yq = Q(T(x))                      written to yq[rows][d] (same dtype; T(x) is rounded to the
+ *                                       storage type before it is quantised, Q as in model_mx_quantize),
+ *     r  = x - T^-1(yq),  T^-1(y) = A^-1 y - A^-1 v   (never stored),
+ *     e_blocks[i] = mean over tokens of 1/block * sum over block i of r_j^2   (d/block floats, device),
+ *     e_total[0]  = 1/d * mean over tokens of ||r||^2                          (device).
+ * a_mat = A and a_inv = A^-1 are [d][d] row-major in the tensor's dtype (the caller supplies the inverse),
+ * v and inv_shift = -A^-1 v are binary32 [d].  Both products run on the matrix cores with binary32
+ * accumulation; the quantiser and the squared-error sums are epilogues of the two GEMMs.
+ * workspace: model_transform_mse_workspace bytes of device memory.  block must be 32, d a multiple of
+ * 128, rows a multiple of 256 (bf16) or 128 (fp32), every tensor below 2 GiB: AE_EINVAL otherwise. */
+int model_transform_mse_workspace(int64_t rows, int64_t d, int dtype, int64_t* bytes);
+int model_transform_mse(const void* x, const void* a_mat, const float* v, const void* a_inv, const float* inv_shift,
+                        int64_t rows, int64_t d, int block, int dtype, void* yq, void* workspace, float* e_blocks,
+                        float* e_total, void* stream);
+
 /* Measurement aid: TFLOP/s of a loop of nothing but independent 32x32x16 bf16 matrix-core
  * instructions on every compute unit (two workgroups of four wavefronts each), the practical
  * ceiling beside the nominal peak; with lds_reads = 6 each wavefront also reads the six 16-byte

@@ -22,7 +22,8 @@ SYMBOLS = [
     "model_describe", "model_create", "model_destroy", "model_param_count", "model_io_shape",
     "model_set_sample_offset", "model_forward", "model_backward", "model_loss_mse", "model_noise",
     "model_pnorm_awgn", "model_gen_bits", "model_count_errors", "model_num_steps", "model_step_info",
-    "model_get_activation", "model_timing_enable", "model_set_overlap", "model_calibrate_mfma", "model_mx_quantize", "model_timing_slots",
+    "model_get_activation", "model_timing_enable", "model_set_overlap", "model_calibrate_mfma", "model_mx_quantize", "model_transform_mse_workspace",
+    "model_transform_mse", "model_timing_slots",
     "model_timing_read", "model_timing_reset", "model_last_error",
 ]
 
@@ -60,6 +61,8 @@ def _load():
     L.model_set_overlap.argtypes = [vp, C.c_int]
     L.model_calibrate_mfma.argtypes = [C.c_int, C.c_int, vp, C.POINTER(C.c_double), vp]
     L.model_mx_quantize.argtypes = [vp, vp, C.c_int64, C.c_int64, C.c_int, C.c_int, vp]
+    L.model_transform_mse_workspace.argtypes = [C.c_int64, C.c_int64, C.c_int, i64p]
+    L.model_transform_mse.argtypes = [vp, vp, vp, vp, vp, C.c_int64, C.c_int64, C.c_int, C.c_int, vp, vp, vp, vp, vp]
     L.model_timing_slots.argtypes = [vp, C.POINTER(C.c_int)]
     L.model_timing_read.argtypes = [vp, C.c_int, C.c_char_p, C.c_int, C.POINTER(C.c_double), i64p,
                                     C.POINTER(C.c_double), C.POINTER(C.c_double)]
@@ -215,6 +218,23 @@ def model_mx_quantize(x, q, rows, d, block=32):
     dtype = AE_BF16 if x.dtype == torch.bfloat16 else AE_F32
     assert x.numel() == rows * d and q.numel() == rows * d and q.dtype == x.dtype
     _check(lib.model_mx_quantize(_ptr(x), _ptr(q), rows, d, block, dtype, _stream()))
+
+
+def model_transform_mse_workspace(rows, d, dtype):
+    n = C.c_int64()
+    _check(lib.model_transform_mse_workspace(rows, d, dtype, C.byref(n)))
+    return n.value
+
+
+def model_transform_mse(x, a_mat, v, a_inv, inv_shift, rows, d, block, yq, workspace, e_blocks, e_total):
+    dtype = AE_BF16 if x.dtype == torch.bfloat16 else AE_F32
+    assert x.numel() == rows * d and yq.numel() == rows * d and a_mat.numel() == d * d and a_inv.numel() == d * d
+    assert a_mat.dtype == x.dtype and a_inv.dtype == x.dtype and yq.dtype == x.dtype
+    assert v.numel() == d and inv_shift.numel() == d and e_blocks.numel() == d // block and e_total.numel() == 1
+    assert workspace.numel() * workspace.element_size() >= model_transform_mse_workspace(rows, d, dtype)
+    _check(lib.model_transform_mse(_ptr(x), _ptr(a_mat), _ptr(v, torch.float32), _ptr(a_inv), _ptr(inv_shift, torch.float32),
+                                   rows, d, block, dtype, _ptr(yq), _ptr(workspace), _ptr(e_blocks, torch.float32),
+                                   _ptr(e_total, torch.float32), _stream()))
 
 
 def model_calibrate_mfma(lds_reads, iters=4000):

@@ -51,6 +51,11 @@ struct IgemmParams {
   // stored input (one per output parity (a, b) = (phase>>1, phase&1), pads 1-a and 1-b, weights
   // w + phase*N*K); row (n, i, j) of phase (a, b) is output pixel (2i+a, 2j+b) of a 2Hc x 2Wc image
   int phases;
+  // epilogue variants of the dense-GEMM use (EPI template parameter of k_igemm):
+  //   1: the stored output is MX block-quantised (blocks of 32 output columns, FP4 E2M1 elements);
+  //   2: nothing is stored; the epilogue forms resid[m][n] - (acc + bias) and leaves per-tile column sums of it
+  //      and of its square in `partial` (resid: [M][N] in the storage type)
+  const void* resid;
 };
 
 // output row (pixel index in y) of GEMM row m
@@ -110,7 +115,7 @@ template <> __device__ __forceinline__ void mma_step<float>(const uint4v& a, con
 // Epilogue of a tile that lies wholly inside the output (no bounds checks): bias, rounding to the
 // storage type, optional column statistics of the stored value, optional ReLU, then 16-byte
 // row stores staged through this wave's LDS area.
-template <typename T, int MI, int NJ, int WN, int SW, bool STATS, bool RELU>
+template <typename T, int MI, int NJ, int WN, int SW, bool STATS, bool RELU, bool MXQ = false>
 __device__ __forceinline__ void igemm_store_interior(const floatx16 (&acc)[MI][NJ], const float (&bias)[NJ], T* stage,
                                                      T* yrow, int N, int lane, float (&s1)[NJ], float (&s2)[NJ],
                                                      const IgemmParams& p, int64_t mrow0, int phase, T* ycol) {
@@ -137,9 +142,45 @@ __device__ __forceinline__ void igemm_store_interior(const floatx16 (&acc)[MI][N
       const int lr = idx / CPRO, ch = idx % CPRO;
       T* dst = p.phases == 1 ? yrow + (int64_t)(i * 32 + lr) * N + ch * EPC
                              : ycol + igemm_out_row(p, mrow0 + i * 32 + lr, phase) * N + ch * EPC;
-      *reinterpret_cast<uint4v*>(dst) = *reinterpret_cast<const uint4v*>(&stage[lr * SW + ch * EPC]);
+      if constexpr (MXQ) {
+        // MX block quantisation of the stored row: a block of 32 columns is 32/EPC neighbouring lanes of this pass
+        float f[EPC];
+        Store<T>::ldv(&stage[lr * SW + ch * EPC], f);
+        float amax = 0.0f;
+#pragma unroll
+        for (int t = 0; t < EPC; ++t) amax = fmaxf(amax, fabsf(f[t]));
+#pragma unroll
+        for (int off = 1; off < 32 / EPC; off <<= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
+        if (amax > 0.0f) {
+          const int k = mx_scale_exp(amax);
+          const float sc = ldexpf(1.0f, k), inv_sc = ldexpf(1.0f, -k);
+#pragma unroll
+          for (int t = 0; t < EPC; ++t) f[t] = mx_quant_e2m1(f[t], inv_sc, sc);
+        }
+        Store<T>::stv(dst, f);
+      } else {
+        *reinterpret_cast<uint4v*>(dst) = *reinterpret_cast<const uint4v*>(&stage[lr * SW + ch * EPC]);
+      }
     }
   }
+}
+
+// Epilogue variant 2: column sums of resid - (acc + bias) and of its square over the tile's rows; nothing stored.
+template <typename T, int MI, int NJ>
+__device__ __forceinline__ void igemm_resid_stats(const floatx16 (&acc)[MI][NJ], const float (&bias)[NJ], const T* rrow, int N,
+                                                  int lane, float (&s1)[NJ], float (&s2)[NJ]) {
+  const int col_lane = lane & 31, row_lane = (lane >> 5) * 4;
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int lr = (e >> 2) * 8 + row_lane + (e & 3);
+        const float dv = Store<T>::ld(rrow + (int64_t)(i * 32 + lr) * N + j * 32 + col_lane) - (acc[i][j][e] + bias[j]);
+        s1[j] += dv;
+        s2[j] = fmaf(dv, dv, s2[j]);
+      }
 }
 
 // Epilogue shared by the implicit-GEMM kernels.  Accumulator element e of lane l in tile (i,j):
@@ -147,7 +188,7 @@ __device__ __forceinline__ void igemm_store_interior(const floatx16 (&acc)[MI][N
 // Results go through a wave-private LDS staging area (the operand buffers are free: the K loop
 // ended on a barrier) so that global stores are 16 bytes wide and each instruction covers
 // whole row segments.  smem: at least 4*32*(WN + 16/sizeof(T))*sizeof(T) bytes; sRed: [WGM][2][BN].
-template <typename T, int BM, int BN, int WGM, int WGN, bool INTERIOR>
+template <typename T, int BM, int BN, int WGM, int WGN, bool INTERIOR, int EPI = 0>
 __device__ __forceinline__ void igemm_epilogue(floatx16 (&acc)[BM / WGM / 32][BN / WGN / 32], const IgemmParams& p,
                                                char* smem, float (*sRed)[2][BN], int64_t m0, int n0, int64_t tile_m,
                                                int phase = 0) {
@@ -171,7 +212,11 @@ __device__ __forceinline__ void igemm_epilogue(floatx16 (&acc)[BM / WGM / 32][BN
     T* yrow = Y + (m0 + wm * WM) * p.N + n0 + wn * WN;
     T* ycol = Y + n0 + wn * WN;
     const int64_t mrow0 = m0 + wm * WM;
-    if (p.partial) igemm_store_interior<T, MI, NJ, WN, SW, true, false>(acc, bias, stage, yrow, p.N, lane, s1, s2, p, mrow0, phase, ycol);
+    if constexpr (EPI == 1)
+      igemm_store_interior<T, MI, NJ, WN, SW, false, false, true>(acc, bias, stage, yrow, p.N, lane, s1, s2, p, mrow0, phase, ycol);
+    else if constexpr (EPI == 2)
+      igemm_resid_stats<T, MI, NJ>(acc, bias, (const T*)p.resid + (m0 + wm * WM) * p.N + n0 + wn * WN, p.N, lane, s1, s2);
+    else if (p.partial) igemm_store_interior<T, MI, NJ, WN, SW, true, false>(acc, bias, stage, yrow, p.N, lane, s1, s2, p, mrow0, phase, ycol);
     else if (p.act == ACT_RELU) igemm_store_interior<T, MI, NJ, WN, SW, false, true>(acc, bias, stage, yrow, p.N, lane, s1, s2, p, mrow0, phase, ycol);
     else igemm_store_interior<T, MI, NJ, WN, SW, false, false>(acc, bias, stage, yrow, p.N, lane, s1, s2, p, mrow0, phase, ycol);
   } else {
@@ -323,8 +368,9 @@ struct SlabReads<KS, KS, MI, NJ, BKB> {
 // registers.  A wave waits for its own loads of the slab it is about to read (vmcnt), then
 // the workgroup barrier makes every wave's loads visible and also guarantees that the stage
 // about to be refilled has been read by everybody.
-template <typename T, int BM, int BN, int WGM, int WGN, int BKB, bool INTERIOR, bool DMA>
+template <typename T, int BM, int BN, int WGM, int WGN, int BKB, bool INTERIOR, bool DMA, int EPI = 0>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k_igemm(IgemmParams p) {
+  static_assert(EPI == 0 || INTERIOR, "the special epilogues exist for check-free tiles only");
   static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
   static_assert(BKB == 64 || BKB == 128, "slab row bytes");
   constexpr int ES = (int)sizeof(T);
@@ -525,7 +571,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
       return;
     }
   }
-  igemm_epilogue<T, BM, BN, WGM, WGN, INTERIOR>(acc, p, smem, sRed, m0, n0, tile_m, phase);
+  igemm_epilogue<T, BM, BN, WGM, WGN, INTERIOR, EPI>(acc, p, smem, sRed, m0, n0, tile_m, phase);
 }
 
 // y = act(round(sum over splits of partial[split] + bias)) for split-K launches
@@ -829,7 +875,7 @@ int conv_partial_rows(const ConvArgs& a, bool mfma) {
 
 // Split-K: layers with fewer than 128 output tiles (small batch x fully-connected) and a long K.
 static int conv_mfma_splits(const ConvArgs& a0) {
-  if (a0.partial || a0.geom == CONV_UP_PHASES || !conv_mfma_supported(a0) || conv3_patch_usable(a0)) return 1;
+  if (a0.partial || a0.epi != CONV_EPI_NONE || a0.geom == CONV_UP_PHASES || !conv_mfma_supported(a0) || conv3_patch_usable(a0)) return 1;
   const ConvArgs a = conv_effective(a0);
   const int es = (int)dtype_size(a.dtype);
   const int64_t M = (int64_t)a.n * a.hc * a.wc;
@@ -863,6 +909,17 @@ bool conv_up_phases_usable(const ConvArgs& a0) {
   return (M / t.bm) * (e.cout / t.bn) * 4 >= 256;
 }
 
+// The special epilogues: 1x1 layers, check-free tiles of the shapes they are instantiated for, no split-K.
+bool conv_epi_usable(const ConvArgs& a) {
+  if (a.epi == CONV_EPI_NONE) return true;
+  if (a.geom != CONV_PLAIN || a.k != 1 || a.up != 0 || a.hc != 1 || a.wc != 1 || !conv_mfma_supported(a)) return false;
+  if (a.y_aux || a.act != ACT_NONE || a.cout % 128 != 0) return false;
+  if (a.epi == CONV_EPI_RESID && (!a.partial || !a.resid)) return false;
+  if (a.epi == CONV_EPI_MXQ && a.partial) return false;
+  const IgemmTile t = pick_tile(a.n, a.cout, a.cin, (int)dtype_size(a.dtype));
+  return t.bn == 128 && a.n % t.bm == 0;
+}
+
 bool conv_up_dgrad_usable(const ConvArgs& a0) {
   if (a0.k != 3 || a0.up != 0 || (a0.hc & 1) || (a0.wc & 1) || a0.partial || a0.y_aux || a0.bias || a0.act != ACT_NONE) return false;
   ConvArgs a = a0;
@@ -873,6 +930,7 @@ bool conv_up_dgrad_usable(const ConvArgs& a0) {
 int launch_conv_mfma(const ConvArgs& a0, hipStream_t s) {
   if (!conv_mfma_supported(a0)) return fail(AE_EINVAL, "conv_mfma: shape not supported");
   if (a0.geom == CONV_UP_PHASES && !conv_up_phases_usable(a0)) return fail(AE_EINVAL, "conv_mfma: phase form not usable here");
+  if (!conv_epi_usable(a0)) return fail(AE_EINVAL, "conv_mfma: epilogue variant not usable for this shape");
   const ConvArgs a = conv_effective(a0);
   const int es = (int)dtype_size(a.dtype);
   IgemmParams p;
@@ -881,6 +939,7 @@ int launch_conv_mfma(const ConvArgs& a0, hipStream_t s) {
   p.N = a.cout; p.K = a.k * a.k * a.cin;
   p.Hc = a.hc; p.Wc = a.wc; p.Cin = a.cin; p.ksz = a.k; p.up = a.up; p.act = a.act;
   p.Hv = a.hc; p.Wv = a.wc; p.stride = 1; p.pad = (a.k - 1) >> 1; p.phases = 1;
+  p.resid = a0.resid;
   p.x_bytes = (unsigned)((int64_t)a.n * (a.hc >> a.up) * (a.wc >> a.up) * a.cin * es);
   p.w_bytes = (unsigned)((int64_t)a.cout * a.k * a.k * a.cin * es);
   if (a0.geom == CONV_UP_PHASES) {
@@ -939,6 +998,18 @@ int launch_conv_mfma(const ConvArgs& a0, hipStream_t s) {
     if (a.dtype == AE_BF16) IGEMM_LAUNCH_T(bf16_t, BMV, BNV, GM, GN);          \
     else IGEMM_LAUNCH_T(float, BMV, BNV, GM, GN);                              \
   } while (0)
+  if (a0.epi != CONV_EPI_NONE) {
+    // (conv_epi_usable: interior tiles, BN = 128, no split)
+#define IGEMM_LAUNCH_EPI(T, BMV, E) hipLaunchKernelGGL((k_igemm<T, BMV, 128, 2, 2, 64, true, true, E>), grid, dim3(256), 0, s, p)
+    if (a.dtype == AE_BF16) {
+      if (t.bm == 256) { if (a0.epi == CONV_EPI_MXQ) IGEMM_LAUNCH_EPI(bf16_t, 256, 1); else IGEMM_LAUNCH_EPI(bf16_t, 256, 2); }
+      else { if (a0.epi == CONV_EPI_MXQ) IGEMM_LAUNCH_EPI(bf16_t, 128, 1); else IGEMM_LAUNCH_EPI(bf16_t, 128, 2); }
+    } else {
+      if (a0.epi == CONV_EPI_MXQ) IGEMM_LAUNCH_EPI(float, 128, 1); else IGEMM_LAUNCH_EPI(float, 128, 2);
+    }
+#undef IGEMM_LAUNCH_EPI
+    return launch_status("conv_mfma_epi");
+  }
   if (t.bm == 256 && t.bn == 128) IGEMM_LAUNCH_K(bf16_t, 256, 128, 2, 2, 64);
   else if (t.bm == 256) IGEMM_LAUNCH_K(bf16_t, 256, 64, 4, 1, 64);
   else if (t.bn == 128) IGEMM_LAUNCH(128, 128, 2, 2);

@@ -92,4 +92,22 @@ __device__ __forceinline__ float apply_act(float v, int act) {
   return v;
 }
 
+// ---- MX block quantisation (the paper's Eq. 1) with FP4 E2M1 elements, shared by the stand-alone kernel
+// and the GEMM epilogue that quantises its output ----
+// scale exponent of a block from its largest magnitude (> 0): floor(log2 amax) - r_max (r_max = 2),
+// clamped to the E8M0 range
+__device__ __forceinline__ int mx_scale_exp(float amax) {
+  int k = ilogbf(amax) - 2;                      // subnormal maxima included
+  k = k < -127 ? -127 : k;
+  return k > 127 ? 127 : k;
+}
+// s * Q_e(v / s) for s = 2^k: nearest E2M1 magnitude, ties to even, saturating at 6
+__device__ __forceinline__ float mx_quant_e2m1(float v, float inv_s, float s) {
+  const float y = v * inv_s;                     // exact (power of two), |y| < 8
+  const float a = fabsf(y);
+  float r = a < 2.0f ? rintf(a * 2.0f) * 0.5f : (a < 4.0f ? rintf(a) : rintf(a * 0.5f) * 2.0f);
+  r = fminf(r, 6.0f);
+  return copysignf(r, y) * s;                    // at most two significant bits times a power of two: exact
+}
+
 }  // namespace ae

@@ -139,8 +139,16 @@ struct ConvArgs {
   //                   (x = dY [n][hc][wc][cin], y = dX [n][hc/2][wc/2][cout], w = [cout][4][4][cin]),
   //                   which also replaces the 2x2 sum over each upsampled pixel.
   int geom = 0;
+  // Dense-GEMM epilogues (k = 1 layers whose tiles all lie inside the output, no split-K):
+  //   CONV_EPI_MXQ    the stored output is MX block-quantised (blocks of 32 columns, FP4 E2M1 elements);
+  //   CONV_EPI_RESID  nothing is stored: `partial` receives, per row tile, the column sums of
+  //                   resid - (x w^T + bias) and of its square (resid: [rows][cout] in the storage type).
+  int epi = 0;
+  const void* resid = nullptr;
 };
 enum { CONV_PLAIN = 0, CONV_UP_PHASES = 1, CONV_UP_DGRAD = 2 };
+enum { CONV_EPI_NONE = 0, CONV_EPI_MXQ = 1, CONV_EPI_RESID = 2 };
+bool conv_epi_usable(const ConvArgs& a);         // can launch_conv_mfma run a.epi for this shape?
 bool conv_up_phases_usable(const ConvArgs& a);   // a: the plain description (geom ignored)
 bool conv_up_dgrad_usable(const ConvArgs& a);    // a: the plain description of the input-gradient conv at conv resolution
 // Summed weights of the two forms above from the canonical [cout][cin][3][3] fp32 weights.

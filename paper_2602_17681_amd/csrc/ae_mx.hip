@@ -9,6 +9,7 @@
 // binary32 (scaling by powers of two; rounding to a grid of at most two significant bits), so
 // the result does not depend on the order of anything and is compared bit for bit.
 #include <hip/hip_runtime.h>
+#include <string.h>
 
 #include "ae_device.h"
 #include "ae_internal.h"
@@ -17,22 +18,6 @@ namespace ae {
 namespace {
 
 constexpr int NT = 256;
-
-// scale exponent of a block from its largest magnitude (> 0)
-__device__ __forceinline__ int mx_scale_exp(float amax) {
-  int k = ilogbf(amax) - 2;                      // floor(log2 amax) - r_max, subnormal maxima included
-  k = k < -127 ? -127 : k;
-  return k > 127 ? 127 : k;
-}
-
-// s * Q_e(v / s) for s = 2^k: nearest E2M1 magnitude, ties to even, saturating
-__device__ __forceinline__ float mx_quant_e2m1(float v, float inv_s, float s) {
-  const float y = v * inv_s;                     // exact (power of two), |y| < 8
-  const float a = fabsf(y);
-  float r = a < 2.0f ? rintf(a * 2.0f) * 0.5f : (a < 4.0f ? rintf(a) : rintf(a * 0.5f) * 2.0f);
-  r = fminf(r, 6.0f);
-  return copysignf(r, y) * s;                    // at most two significant bits times a power of two: exact
-}
 
 // Vector path: a lane owns 16 bytes (V elements); the LPB = B / V lanes of a block are neighbours
 // in a wavefront and find the block maximum with xor-shuffles.
@@ -106,8 +91,82 @@ int launch_mx(const void* x, void* q, int64_t total, int block, hipStream_t s) {
   return launch_status("mx_quantize");
 }
 
+// Block errors from the per-tile column sums of squares: eb[i] = 1/(rows*block) * sum over tiles and over the
+// block's columns of partial[tile][1][column], added in a fixed order in double; one workgroup per block.
+__global__ void k_mse_blocks(const float* __restrict__ partial, int tiles, int N, int block, double inv, float* __restrict__ eb) {
+  __shared__ double sm[NT / 64 + 1];
+  const int i = blockIdx.x;
+  double acc = 0.0;
+  const int64_t items = (int64_t)tiles * block;
+  for (int64_t it = threadIdx.x; it < items; it += NT) {
+    const int64_t t = it / block;
+    const int j = (int)(it - t * block);
+    acc += (double)partial[(t * 2 + 1) * N + (int64_t)i * block + j];
+  }
+  acc = block_sum<NT>(acc, sm);
+  if (threadIdx.x == 0) eb[i] = (float)(acc * inv);
+}
+// E = mean of the block errors (one workgroup, fixed order)
+__global__ void k_mse_total(const float* __restrict__ eb, int nb, float* __restrict__ e) {
+  __shared__ double sm[NT / 64 + 1];
+  double acc = 0.0;
+  for (int i = threadIdx.x; i < nb; i += NT) acc += (double)eb[i];
+  acc = block_sum<NT>(acc, sm);
+  if (threadIdx.x == 0) *e = (float)(acc / (double)nb);
+}
+
+int transform_tile_rows(int64_t rows, int64_t d, int dtype) {
+  ConvArgs a;
+  memset(&a, 0, sizeof(a));
+  a.n = (int)rows; a.hc = a.wc = 1; a.cin = a.cout = (int)d; a.k = 1; a.dtype = dtype;
+  return conv_partial_rows(a, true);
+}
+
 }  // namespace
 }  // namespace ae
+
+extern "C" int model_transform_mse_workspace(int64_t rows, int64_t d, int dtype, int64_t* bytes) {
+  using namespace ae;
+  if (!bytes || rows <= 0 || d <= 0 || (dtype != AE_F32 && dtype != AE_BF16)) return fail(AE_EINVAL, "model_transform_mse_workspace: bad argument");
+  if (rows >= 0x7FFFFFFF || d >= 0x7FFFFFFF) return fail(AE_EINVAL, "model_transform_mse_workspace: tensor too large");
+  const int64_t tiles = (rows + transform_tile_rows(rows, d, dtype) - 1) / transform_tile_rows(rows, d, dtype);
+  *bytes = tiles * 2 * d * 4;
+  return AE_OK;
+}
+
+extern "C" int model_transform_mse(const void* x, const void* a_mat, const float* v, const void* a_inv, const float* inv_shift,
+                                   int64_t rows, int64_t d, int block, int dtype, void* yq, void* workspace,
+                                   float* e_blocks, float* e_total, void* stream) {
+  using namespace ae;
+  if (!x || !a_mat || !v || !a_inv || !inv_shift || !yq || !workspace || !e_blocks || !e_total)
+    return fail(AE_EINVAL, "model_transform_mse: null argument");
+  if (dtype != AE_F32 && dtype != AE_BF16) return fail(AE_EINVAL, "model_transform_mse: bad dtype");
+  if (rows <= 0 || d <= 0 || rows >= 0x7FFFFFFF || d >= 0x7FFFFFFF) return fail(AE_EINVAL, "model_transform_mse: bad size");
+  if (block != 32) return fail(AE_EINVAL, "model_transform_mse: the fused epilogue quantises blocks of 32");
+  hipStream_t s = (hipStream_t)stream;
+  ConvArgs g1;
+  memset(&g1, 0, sizeof(g1));
+  g1.x = x; g1.w = a_mat; g1.bias = v; g1.y = yq;
+  g1.n = (int)rows; g1.hc = g1.wc = 1; g1.cin = g1.cout = (int)d; g1.k = 1; g1.up = 0; g1.act = ACT_NONE; g1.dtype = dtype;
+  g1.epi = CONV_EPI_MXQ;
+  if (!conv_epi_usable(g1))
+    return fail(AE_EINVAL, "model_transform_mse: d must be a multiple of 128 and rows a multiple of the row tile (256 bf16 / 128 fp32), tensors below 2 GiB");
+  // T(x) = x A^T + v, rounded to the storage type and MX-quantised in the GEMM's epilogue
+  AE_TRY(launch_conv_mfma(g1, s));
+  // T^-1(Q(T x)) = yq A^-T - A^-1 v is never stored: the second GEMM's epilogue forms x - T^-1(...) and its column sums of squares
+  ConvArgs g2 = g1;
+  g2.x = yq; g2.w = a_inv; g2.bias = inv_shift; g2.y = nullptr;
+  g2.epi = CONV_EPI_RESID; g2.resid = x; g2.partial = (float*)workspace;
+  if (!conv_epi_usable(g2)) return fail(AE_EINVAL, "model_transform_mse: shape not supported");
+  AE_TRY(launch_conv_mfma(g2, s));
+  const int tile_rows = transform_tile_rows(rows, d, dtype);
+  const int tiles = (int)(rows / tile_rows);
+  const int nb = (int)(d / block);
+  hipLaunchKernelGGL(k_mse_blocks, dim3(nb), dim3(NT), 0, s, (const float*)workspace, tiles, (int)d, block,
+                     1.0 / ((double)rows * (double)block), e_blocks);
+  hipLaunchKernelGGL(k_mse_total, dim3(1), dim3(NT), 0, s, e_blocks, nb, e_total);
+  return launch_status("transform_mse");
+}
 
 extern "C" int model_mx_quantize(const void* x, void* q, int64_t rows, int64_t d, int block, int dtype, void* stream) {
   using namespace ae;

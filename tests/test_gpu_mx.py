@@ -116,3 +116,79 @@ def test_full_size_sampled_rows(ae, dtype):
     ratio = (qb.abs() / s).flatten()
     grid = torch.tensor([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0], device="cuda")
     assert bool(torch.isin(ratio, grid).all())
+
+
+# ------------------------------------------------------------------ transformation mean squared error (Eq. 2)
+def _run_tmse(ae, x, a, v, ainv, ishift, dtype):
+    import torch
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    rows, d = x.shape
+    dev = lambda arr, t=td: torch.from_numpy(np.ascontiguousarray(arr, dtype=np.float32)).cuda().to(t).contiguous()
+    xt, at, ait = dev(x), dev(a), dev(ainv)
+    vt, st = dev(v, torch.float32), dev(ishift, torch.float32)
+    yq = torch.full_like(xt, float("nan"))
+    ws = torch.empty(ae.model_transform_mse_workspace(rows, d, ae.DTYPES[dtype]) // 4, dtype=torch.float32, device="cuda")
+    eb = torch.full((d // 32,), float("nan"), device="cuda")
+    et = torch.full((1,), float("nan"), device="cuda")
+    ae.model_transform_mse(xt, at, vt, ait, st, rows, d, 32, yq, ws, eb, et)
+    torch.cuda.synchronize()
+    return float(et.item()), eb.cpu().numpy().astype(np.float64), yq.float().cpu().numpy()
+
+
+# binary32 accumulation against float64 moves T(x) by ~1e-6 relative; where that crosses a rounding boundary of the
+# storage type (bf16: 5e-4 of the elements) or of the quantiser, one element's result moves by a step.  Hence: the
+# quantised tensors agree except for a small fraction of elements, the errors to 1e-4 (fp32) / 5e-3 (bf16).
+TMSE_TOL = {"f32": (1e-4, 1e-4), "bf16": (5e-3, 3e-3)}
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("rows,d,kind", [(256, 128, "identity"), (512, 256, "hadamard"), (768, 384, "affine"), (1024, 1024, "affine")])
+def test_transform_mse_matches_oracle(ae, dtype, rows, d, kind):
+    bf = dtype == "bf16"
+    x = wl.make_activations(rows, d, seed=rows + d, bf16=bf)
+    a, v, ainv, ishift = wl.make_transform(d, seed=d, bf16=bf, kind=kind)
+    e, eb, yq = _run_tmse(ae, x, a, v, ainv, ishift, dtype)
+    e_o, eb_o, yq_o = mxo.transform_mse(x, a, v, ainv, 32, storage=dtype)
+    tol, frac = TMSE_TOL[dtype]
+    differ = np.mean(yq != yq_o.astype(np.float32))
+    assert differ <= frac, differ
+    assert abs(e - e_o) <= tol * e_o, (e, e_o)
+    assert np.all(np.abs(eb - eb_o) <= 2 * tol * eb_o + 1e-30), np.max(np.abs(eb - eb_o) / eb_o)
+    assert abs(eb.mean() - e) <= 1e-5 * e
+    if kind == "identity":
+        assert _same_bits(yq, mxo.mx_quantize(x.astype(np.float64), 32).astype(np.float32))       # T = id: plain Q(x), bit for bit
+
+
+def test_transform_mse_rejects_unsupported_shapes(ae):
+    import torch
+    t = torch.zeros(256 * 128, device="cuda")
+    p = C.c_void_p(t.data_ptr())
+    call = lambda rows, d, block, dtype=0: ae.lib.model_transform_mse(p, p, p, p, p, rows, d, block, dtype, p, p, p, p, None)
+    assert call(256, 128, 16) == -1            # block size
+    assert call(100, 128, 32) == -1            # rows not a multiple of the row tile
+    assert call(256, 96, 32) == -1             # d not a multiple of 128
+    assert call(256, 128, 32, 5) == -1         # dtype
+    assert ae.lib.model_transform_mse(None, p, p, p, p, 256, 128, 32, 0, p, p, p, p, None) == -1
+    n = C.c_int64()
+    assert ae.lib.model_transform_mse_workspace(0, 128, 0, C.byref(n)) == -1
+
+
+@pytest.mark.parametrize("dtype", ["bf16"])
+def test_transform_mse_full_size(ae, dtype):
+    """The launch bench.py times (16 384 tokens x 4 096 channels, bf16): quantised rows sampled against the oracle, the
+    errors against the oracle on those rows via a second launch on the sample, and E = mean of the block errors."""
+    bf = dtype == "bf16"
+    rows, d = 16384, 4096
+    x = wl.make_activations(rows, d, seed=9, bf16=bf)
+    a, v, ainv, ishift = wl.make_transform(d, seed=9, bf16=bf, kind="affine")
+    e, eb, yq = _run_tmse(ae, x, a, v, ainv, ishift, dtype)
+    assert np.isfinite(e) and abs(eb.mean() - e) <= 1e-5 * e
+    pick = np.sort(np.random.default_rng(4).choice(rows, size=512, replace=False))
+    e_o, eb_o, yq_o = mxo.transform_mse(x[pick], a, v, ainv, 32, storage=dtype)
+    tol, frac = TMSE_TOL[dtype]
+    assert np.mean(yq[pick] != yq_o.astype(np.float32)) <= frac
+    # the same 512 tokens as a launch of their own: their errors against the oracle's
+    e_s, eb_s, _ = _run_tmse(ae, x[pick], a, v, ainv, ishift, dtype)
+    assert abs(e_s - e_o) <= tol * e_o and np.all(np.abs(eb_s - eb_o) <= 2 * tol * eb_o + 1e-30)
+    # and the full launch is consistent with its sample: token averages of heavy-tailed errors over 512 of 16 384 tokens
+    assert 0.5 * e_o < e < 2.0 * e_o

@@ -188,3 +188,33 @@ def make_activations(rows, d, seed, bf16=False):
     tok = np.exp(0.5 * rng.standard_normal((rows, 1)).astype(np.float32))
     x = x * chan[None, :] * tok
     return round_to_bf16(x) if bf16 else x
+
+
+def make_transform(d, seed, bf16=False, kind="affine"):
+    """An invertible d x d matrix A, a shift v, A^-1 and -A^-1 v for the transformation-error path (float32
+    arrays; the inverse is taken in float64 of the matrix AS STORED, then stored in the same type).
+    kind: "identity", "hadamard" (orthonormal Walsh-Hadamard, d a power of two), "affine" (a random
+    rotation times per-channel gains in [0.5, 2], plus a dense perturbation, with a shift)."""
+    rng = np.random.default_rng([seed, 0x7A4F])
+    if kind == "identity":
+        a = np.eye(d)
+        v = np.zeros(d)
+    elif kind == "hadamard":
+        a = np.array([[1.0]])
+        while a.shape[0] < d:
+            a = np.block([[a, a], [a, -a]])
+        a = a / np.sqrt(d)
+        v = np.zeros(d)
+    else:
+        q, _ = np.linalg.qr(rng.standard_normal((d, d)))
+        a = q * np.exp(rng.uniform(-0.7, 0.7, size=d))[None, :] + 0.02 * rng.standard_normal((d, d)) / np.sqrt(d)
+        v = 0.5 * rng.standard_normal(d)
+    a = a.astype(np.float32)
+    if bf16:
+        a = round_to_bf16(a)
+    ainv = np.linalg.inv(a.astype(np.float64)).astype(np.float32)
+    if bf16:
+        ainv = round_to_bf16(ainv)
+    v = v.astype(np.float32)
+    inv_shift = (-(ainv.astype(np.float64) @ v.astype(np.float64))).astype(np.float32)
+    return a, v, ainv, inv_shift
