@@ -190,6 +190,71 @@ def bench_mx_quant(torch, ae, args):
     }
 
 
+# measured HBM bytes per launch of the two GEMMs of the transformation error (profiles/transform_mse.md)
+TMSE_TRAFFIC_BYTES = {"bf16": 1.396e9}   # average of the two GEMM launches (1.301 GB and 1.491 GB)
+
+
+def bench_transform_mse(torch, ae, args):
+    """One step = E(T) of Eq. (2) for a [16 384][4 096] activation tensor resident in HBM and a dense affine map T:
+    y = Q(x A^T + v) and the residual x - T^-1(y), two 16 384 x 4 096 x 4 096 GEMMs on the matrix cores with the
+    quantiser and the error sums in their epilogues.  Algorithmic FLOPs: 2 * 2 * tokens * d^2."""
+    rows, d, block = 16384, 4096, 32
+    bf = args.dtype == "bf16"
+    td = torch.bfloat16 if bf else torch.float32
+    x_h = wl.make_activations(rows, d, seed=9, bf16=bf)
+    a, v, ainv, ishift = wl.make_transform(d, seed=9, bf16=bf, kind="affine")
+    dev = lambda arr, t: torch.from_numpy(np.ascontiguousarray(arr, dtype=np.float32)).cuda().to(t).contiguous()
+    x, at, ait = dev(x_h, td), dev(a, td), dev(ainv, td)
+    vt, st = dev(v, torch.float32), dev(ishift, torch.float32)
+    yq = torch.empty_like(x)
+    ws = torch.empty(ae.model_transform_mse_workspace(rows, d, ae.DTYPES[args.dtype]) // 4, dtype=torch.float32, device="cuda")
+    eb = torch.empty(d // block, device="cuda")
+    et = torch.empty(1, device="cuda")
+    step = lambda: ae.model_transform_mse(x, at, vt, ait, st, rows, d, block, yq, ws, eb, et)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    step_ms = e0.elapsed_time(e1) / args.steps
+    flops = 2.0 * 2.0 * rows * d * d
+    ach = flops / step_ms / 1e9
+    es = x.element_size()
+    import oracle.mx_oracle as mxo
+    sample = 64 if args.no_cpu_baseline else 8192
+    c0 = time.perf_counter()
+    e_o, _, _ = mxo.transform_mse(x_h[:sample], a, v, ainv, block, storage=args.dtype)
+    ct = time.perf_counter() - c0
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = 1
+    return {
+        "metric": "tokens/sec, transformation error E(T) of an affine map under MX quantisation", "value": rows * args.steps / dt,
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
+        "config": {"workload": "transform_mse: E(T), dense affine T, FP4 E2M1 elements, block 32", "tokens": rows, "d": d,
+                   "block": block, "E": float(et.item())},
+        # both GEMM launches together (the two finalising kernels, a few microseconds, are inside the events)
+        "roofline": {"bound": "mfma", "kernel": "k_igemm (quantising / residual epilogues)", "achieved": ach, "peak": PEAK[args.dtype],
+                     "unit": "TFLOP/s", "frac": ach / PEAK[args.dtype], "traffic": TMSE_TRAFFIC_BYTES.get(args.dtype),
+                     "avg_ms": step_ms / 2, "launches_per_step": 2, "flops_per_launch": flops / 2,
+                     "bytes_per_launch": (2.0 * rows * d + d * d) * es},
+        "cpu_baseline": {"value": sample / ct, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+                         "sample": "%d tokens of the same tensor, %.1f s, E=%.4g" % (sample, ct, e_o)},
+    }
+
+
 def cpu_baseline(name, budget_s=20.0):
     """The oracle as it stands, on a bounded sample of the same workload (same layer list and
     resolution, smaller batch), timed on this machine's host cores."""
@@ -239,6 +304,9 @@ def main():
     ap.add_argument("--mx-quant", action="store_true",
                     help="benchmark the MX block quantiser Q(x) (blocks of 32, FP4 E2M1 elements) on 65 536 tokens x 4 096 "
                          "channels of synthetic activations instead of a network: one JSON line with roofline and cpu_baseline")
+    ap.add_argument("--transform-mse", action="store_true",
+                    help="benchmark the transformation error E(T) of Eq. (2) (dense affine map, MX quantiser) on 16 384 tokens x "
+                         "4 096 channels instead of a network: one JSON line with roofline and cpu_baseline")
     ap.add_argument("--calibrate-mfma", action="store_true",
                     help="only run the library's plain matrix-core loop (with and without LDS fragment reads) and exit")
     ap.add_argument("--channel-sweep", action="store_true",
@@ -264,12 +332,16 @@ def main():
     if args.mx_quant:
         print(json.dumps(bench_mx_quant(torch, ae, args)))
         return
+    if args.transform_mse:
+        print(json.dumps(bench_transform_mse(torch, ae, args)))
+        return
     if args.calibrate_mfma:
-        plain = max(ae.model_calibrate_mfma(0) for _ in range(3))
-        with_lds = max(ae.model_calibrate_mfma(6) for _ in range(3))
-        print(json.dumps({"kernel": "k_calib_mfma", "nominal_peak_tflops": PEAK["bf16"], "mfma_only_tflops": round(plain, 1),
-                          "mfma_with_6_lds_reads_per_8_tflops": round(with_lds, 1),
-                          "frac_of_nominal": [round(plain / PEAK["bf16"], 3), round(with_lds / PEAK["bf16"], 3)]}))
+        res = {"kernel": "k_calib_mfma", "nominal_peak_tflops": PEAK["bf16"]}
+        for key, reads, rnd in (("mfma_only_ones", 0, 0), ("mfma_6_lds_reads_per_8_ones", 6, 0),
+                                ("mfma_only_random", 0, 1), ("mfma_6_lds_reads_per_8_random", 6, 1)):
+            tf, mhz = max(ae.model_calibrate_mfma(reads, rnd, iters=40000) for _ in range(3))
+            res[key] = {"tflops": round(tf, 1), "shader_mhz": round(mhz), "frac_of_nominal": round(tf / PEAK["bf16"], 3)}
+        print(json.dumps(res))
         return
     if args.channel_sweep:
         # the channel step moves 2 elements per latent element (read z, write y; the noise is generated, never

@@ -207,12 +207,17 @@ int model_transform_mse(const void* x, const void* a_mat, const float* v, const 
                         float* e_total, void* stream);
 
 /* Measurement aid: TFLOP/s of a loop of nothing but independent 32x32x16 bf16 matrix-core
- * instructions on every compute unit (two workgroups of four wavefronts each), the practical
- * ceiling beside the nominal peak; with lds_reads = 6 each wavefront also reads the six 16-byte
- * fragments per lane that eight such instructions need in a 128x64 wave tile.  Synchronous:
- * times `iters` iterations with HIP events on `stream` and waits.  scratch_dev: device memory
- * of at least 1 KiB (never written in practice).  lds_reads is 0 or 6. */
-int model_calibrate_mfma(int lds_reads, int iters, float* scratch_dev, double* tflops, void* stream);
+ * instructions on every compute unit (two workgroups of four wavefronts each, two wavefronts per
+ * SIMD), the practical ceiling beside the nominal peak; with lds_reads = 6 each wavefront also reads
+ * the six 16-byte fragments per lane that eight such instructions need in a 128x64 wave tile.
+ * random_data = 0: every operand is 1.0; 1: operands with random signs, mantissas and exponents
+ * (the shader clock under matrix-core load is power-managed and depends on the operand data).
+ * Synchronous: times `iters` iterations with HIP events on `stream` and waits.  scratch_dev: at least
+ * 2 KiB of 8-byte aligned device memory (its first 16 bytes are written).  shader_mhz (host, may be
+ * null): the shader clock during the loop, from the kernel's cycle counter against its 100 MHz
+ * wall clock.  lds_reads is 0 or 6, iters 1 .. 2^20: AE_EINVAL otherwise. */
+int model_calibrate_mfma(int lds_reads, int random_data, int iters, float* scratch_dev, double* tflops,
+                         double* shader_mhz, void* stream);
 
 const char* model_last_error(void);
 

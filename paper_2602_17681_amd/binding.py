@@ -59,7 +59,7 @@ def _load():
     L.model_get_activation.argtypes = [vp, C.c_int, vp, vp]
     L.model_timing_enable.argtypes = [vp, C.c_int]
     L.model_set_overlap.argtypes = [vp, C.c_int]
-    L.model_calibrate_mfma.argtypes = [C.c_int, C.c_int, vp, C.POINTER(C.c_double), vp]
+    L.model_calibrate_mfma.argtypes = [C.c_int, C.c_int, C.c_int, vp, C.POINTER(C.c_double), C.POINTER(C.c_double), vp]
     L.model_mx_quantize.argtypes = [vp, vp, C.c_int64, C.c_int64, C.c_int, C.c_int, vp]
     L.model_transform_mse_workspace.argtypes = [C.c_int64, C.c_int64, C.c_int, i64p]
     L.model_transform_mse.argtypes = [vp, vp, vp, vp, vp, C.c_int64, C.c_int64, C.c_int, C.c_int, vp, vp, vp, vp, vp]
@@ -237,11 +237,12 @@ def model_transform_mse(x, a_mat, v, a_inv, inv_shift, rows, d, block, yq, works
                                    _ptr(e_total, torch.float32), _stream()))
 
 
-def model_calibrate_mfma(lds_reads, iters=4000):
-    scratch = torch.zeros(256, dtype=torch.float32, device="cuda")
-    out = C.c_double(0.0)
-    _check(lib.model_calibrate_mfma(lds_reads, iters, _ptr(scratch), C.byref(out), _stream()))
-    return out.value
+def model_calibrate_mfma(lds_reads, random_data=0, iters=4000):
+    """(TFLOP/s, shader clock in MHz) of the plain matrix-core loop."""
+    scratch = torch.zeros(512, dtype=torch.float32, device="cuda")
+    out, mhz = C.c_double(0.0), C.c_double(0.0)
+    _check(lib.model_calibrate_mfma(lds_reads, random_data, iters, _ptr(scratch), C.byref(out), C.byref(mhz), _stream()))
+    return out.value, mhz.value
 
 
 def model_gen_bits(seed, first_sample, batch, k, x_pm1):

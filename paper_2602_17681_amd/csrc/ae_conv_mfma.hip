@@ -396,8 +396,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   if (p.phases == 4) { phase = lb0 & 3; lb0 >>= 2; }   // the four phases of a tile run side by side: they read the same input
   const int split = INTERIOR ? 0 : lb0 / p.tiles_mn;
   const int lb = INTERIOR ? lb0 : lb0 - split * p.tiles_mn;
-  const int tile_n = lb % p.tiles_n;
-  const int64_t tile_m = lb / p.tiles_n;
+  // tile order: groups of kGroupM tile rows are walked column by column, so the workgroups in flight on an XCD
+  // cover a squarish patch of the output (few distinct operand rows per K slab in its L2) instead of a wide strip
+  constexpr int kGroupM = 4;
+  const int gsz = kGroupM * p.tiles_n, grp = lb / gsz, in_grp = lb - grp * gsz;
+  const int gm = min(p.tiles_mn / p.tiles_n - grp * kGroupM, kGroupM);
+  const int tile_n = in_grp / gm;
+  const int64_t tile_m = grp * kGroupM + in_grp % gm;
   const int64_t m0 = tile_m * BM;
   const int n0 = tile_n * BN;
   const int pad_h = p.pad - (phase >> 1), pad_w = p.pad - (phase & 1);

@@ -305,14 +305,18 @@ def test_calibration_loop_and_its_argument_checks(ae):
     hardware (above the fp32 vector peak, not above the datasheet's bf16 peak), and rejects bad arguments."""
     import ctypes as C
     import torch
-    plain = ae.model_calibrate_mfma(0, iters=500)
-    with_lds = ae.model_calibrate_mfma(6, iters=500)
+    plain, mhz = ae.model_calibrate_mfma(0, 0, iters=500)
+    with_lds, _ = ae.model_calibrate_mfma(6, 0, iters=500)
+    rnd, mhz_rnd = ae.model_calibrate_mfma(0, 1, iters=500)
     assert 160.0 < with_lds <= plain * 1.05 and plain < 2500.0 * 1.02, (plain, with_lds)
+    assert 160.0 < rnd <= plain * 1.05 and 500.0 < mhz_rnd < 2600.0 and 500.0 < mhz < 2600.0, (rnd, mhz, mhz_rnd)
     out = C.c_double()
-    scratch = torch.zeros(256, device="cuda")
-    assert ae.lib.model_calibrate_mfma(3, 100, C.c_void_p(scratch.data_ptr()), C.byref(out), None) == -1
-    assert ae.lib.model_calibrate_mfma(0, 0, C.c_void_p(scratch.data_ptr()), C.byref(out), None) == -1
-    assert ae.lib.model_calibrate_mfma(0, 100, None, C.byref(out), None) == -1
+    scratch = torch.zeros(512, device="cuda")
+    sp = C.c_void_p(scratch.data_ptr())
+    assert ae.lib.model_calibrate_mfma(3, 0, 100, sp, C.byref(out), None, None) == -1
+    assert ae.lib.model_calibrate_mfma(0, 0, 0, sp, C.byref(out), None, None) == -1
+    assert ae.lib.model_calibrate_mfma(0, 0, 100, None, C.byref(out), None, None) == -1
+    assert ae.lib.model_calibrate_mfma(0, 0, 100, C.c_void_p(scratch.data_ptr() + 4), C.byref(out), None, None) == -1
 
 
 # ------------------------------------------------------------------ full benchmark sizes
