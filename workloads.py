@@ -218,3 +218,46 @@ def make_transform(d, seed, bf16=False, kind="affine"):
     v = v.astype(np.float32)
     inv_shift = (-(ainv.astype(np.float64) @ v.astype(np.float64))).astype(np.float32)
     return a, v, ainv, inv_shift
+
+
+def make_lu_params(d, seed, kind="random", noise=0.0, block=32):
+    """Free parameters of the LU parametrisation A = P L (U + diag(s)): (Lp, Up, log_s, sign, perm), float32 arrays
+    (perm int32; (P M)[i] = M[perm[i]]).
+    kind "random": a random permutation, dense Gaussian triangles of size 1/sqrt(d), log|s| ~ N(0, 0.3), random signs.
+    kind "bd_hadamard": the paper's initialisation for this parametrisation — A is block diagonal with blocks of
+    `block` x `block` randomly signed orthonormal Hadamard matrices, given here by the exact factors of each block
+    (partial-pivoting LU, a library routine); `noise` > 0 adds Gaussian noise of that size to the free parameters
+    outside the diagonal blocks (reading: the small off-block noise of the initialisation enters through the
+    parameters)."""
+    rng = np.random.default_rng([seed, 0x1D5])
+    if kind == "random":
+        perm = rng.permutation(d).astype(np.int32)
+        lp = rng.standard_normal((d, d)) / np.sqrt(d)
+        up = rng.standard_normal((d, d)) / np.sqrt(d)
+        log_s = 0.3 * rng.standard_normal(d)
+        sign = rng.choice([-1.0, 1.0], size=d)
+    else:
+        import scipy.linalg
+        assert d % block == 0 and block & (block - 1) == 0
+        h = np.array([[1.0]])
+        while h.shape[0] < block:
+            h = np.block([[h, h], [h, -h]])
+        h /= np.sqrt(block)
+        perm = np.zeros(d, dtype=np.int32)
+        lp, up = np.zeros((d, d)), np.zeros((d, d))
+        log_s, sign = np.zeros(d), np.ones(d)
+        for b in range(d // block):
+            hb = h * rng.choice([-1.0, 1.0], size=block)[None, :]           # random column signs
+            pm, l, u = scipy.linalg.lu(hb)                                   # hb = pm @ l @ u
+            o = b * block
+            perm[o:o + block] = o + np.argmax(pm, axis=1)                    # (pm M)[i] = M[argmax_j pm[i, j]]
+            lp[o:o + block, o:o + block] = np.tril(l, -1)
+            up[o:o + block, o:o + block] = np.triu(u, 1)
+            log_s[o:o + block] = np.log(np.abs(np.diag(u)))
+            sign[o:o + block] = np.sign(np.diag(u))
+        if noise > 0.0:
+            off = np.kron(np.eye(d // block), np.ones((block, block))) == 0
+            lp += noise * rng.standard_normal((d, d)) * off
+            up += noise * rng.standard_normal((d, d)) * off
+    f = lambda a: np.ascontiguousarray(a, dtype=np.float32)
+    return f(lp), f(up), f(log_s), f(sign), perm
