@@ -206,6 +206,29 @@ int model_transform_mse(const void* x, const void* a_mat, const float* v, const 
                         int64_t rows, int64_t d, int block, int dtype, void* yq, void* workspace, float* e_blocks,
                         float* e_total, void* stream);
 
+/* LU parametrisation of a learnable invertible matrix (the paper's Section on learning affine transformations,
+ * Eq. 4):  A = P L (U + diag(s)).  Free parameters (device pointers, binary32 master copies): lp, up [d][d]
+ * row-major, of which only the strictly lower part of lp and the strictly upper part of up are read (L has a
+ * unit diagonal, U a zero diagonal); log_s [d] with s = sign_s * exp(log_s) (sign_s [d] holds +-1 and is not
+ * learned); perm [d] (int32): the fixed permutation, (P M)[i] = M[perm[i]] — it must be a permutation of
+ * 0..d-1 (an entry outside that range is treated as i; duplicates give unspecified rows, never an access out
+ * of bounds).  dtype: storage type of the matrix operands and results (AE_F32 or AE_BF16); products run on the
+ * matrix cores with binary32 accumulation.  d: a multiple of 32, 32..16384, else AE_EINVAL.  workspace:
+ * model_lu_workspace bytes of device memory (the same size serves both calls).
+ * model_lu_compose  writes a_out = A [d][d] in dtype.
+ * model_lu_backward given g = dLoss/dA [d][d] in dtype, writes the gradients of the free parameters in binary32:
+ *   d_lp [d][d] (strictly lower part, zero elsewhere), d_up [d][d] (strictly upper part, zero elsewhere),
+ *   d_log_s [d].  The products are rounded to dtype before they are cut to the triangles.
+ * model_vol_penalty the volume regulariser in the form used in practice (Eq. 6 and the paragraph after it):
+ *   *value = (sum_i log_s[i])^2 (device pointer), d_log_s (device, nullable) its gradient 2 sum. */
+int model_lu_workspace(int64_t d, int dtype, int64_t* bytes);
+int model_lu_compose(const float* lp, const float* up, const float* log_s, const float* sign_s, const int* perm,
+                     int64_t d, int dtype, void* a_out, void* workspace, void* stream);
+int model_lu_backward(const void* g, const float* lp, const float* up, const float* log_s, const float* sign_s,
+                      const int* perm, int64_t d, int dtype, float* d_lp, float* d_up, float* d_log_s,
+                      void* workspace, void* stream);
+int model_vol_penalty(const float* log_s, int64_t d, float* value, float* d_log_s, void* stream);
+
 /* Measurement aid: TFLOP/s of a loop of nothing but independent 32x32x16 bf16 matrix-core
  * instructions on every compute unit (two workgroups of four wavefronts each, two wavefronts per
  * SIMD), the practical ceiling beside the nominal peak; with lds_reads = 6 each wavefront also reads

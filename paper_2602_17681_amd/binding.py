@@ -23,7 +23,7 @@ SYMBOLS = [
     "model_set_sample_offset", "model_forward", "model_backward", "model_loss_mse", "model_noise",
     "model_pnorm_awgn", "model_gen_bits", "model_count_errors", "model_num_steps", "model_step_info",
     "model_get_activation", "model_timing_enable", "model_set_overlap", "model_calibrate_mfma", "model_mx_quantize", "model_transform_mse_workspace",
-    "model_transform_mse", "model_timing_slots",
+    "model_transform_mse", "model_lu_workspace", "model_lu_compose", "model_lu_backward", "model_vol_penalty", "model_timing_slots",
     "model_timing_read", "model_timing_reset", "model_last_error",
 ]
 
@@ -63,6 +63,10 @@ def _load():
     L.model_mx_quantize.argtypes = [vp, vp, C.c_int64, C.c_int64, C.c_int, C.c_int, vp]
     L.model_transform_mse_workspace.argtypes = [C.c_int64, C.c_int64, C.c_int, i64p]
     L.model_transform_mse.argtypes = [vp, vp, vp, vp, vp, C.c_int64, C.c_int64, C.c_int, C.c_int, vp, vp, vp, vp, vp]
+    L.model_lu_workspace.argtypes = [C.c_int64, C.c_int, i64p]
+    L.model_lu_compose.argtypes = [vp, vp, vp, vp, vp, C.c_int64, C.c_int, vp, vp, vp]
+    L.model_lu_backward.argtypes = [vp, vp, vp, vp, vp, vp, C.c_int64, C.c_int, vp, vp, vp, vp, vp]
+    L.model_vol_penalty.argtypes = [vp, C.c_int64, vp, vp, vp]
     L.model_timing_slots.argtypes = [vp, C.POINTER(C.c_int)]
     L.model_timing_read.argtypes = [vp, C.c_int, C.c_char_p, C.c_int, C.POINTER(C.c_double), i64p,
                                     C.POINTER(C.c_double), C.POINTER(C.c_double)]
@@ -235,6 +239,38 @@ def model_transform_mse(x, a_mat, v, a_inv, inv_shift, rows, d, block, yq, works
     _check(lib.model_transform_mse(_ptr(x), _ptr(a_mat), _ptr(v, torch.float32), _ptr(a_inv), _ptr(inv_shift, torch.float32),
                                    rows, d, block, dtype, _ptr(yq), _ptr(workspace), _ptr(e_blocks, torch.float32),
                                    _ptr(e_total, torch.float32), _stream()))
+
+
+def model_lu_workspace(d, dtype):
+    n = C.c_int64()
+    _check(lib.model_lu_workspace(d, dtype, C.byref(n)))
+    return n.value
+
+
+def _lu_params(lp, up, log_s, sign_s, perm, d):
+    assert lp.numel() == d * d and up.numel() == d * d and log_s.numel() == d and sign_s.numel() == d and perm.numel() == d
+    return (_ptr(lp, torch.float32), _ptr(up, torch.float32), _ptr(log_s, torch.float32), _ptr(sign_s, torch.float32),
+            _ptr(perm, torch.int32))
+
+
+def model_lu_compose(lp, up, log_s, sign_s, perm, d, a_out, workspace):
+    dtype = AE_BF16 if a_out.dtype == torch.bfloat16 else AE_F32
+    assert a_out.numel() == d * d and workspace.numel() * workspace.element_size() >= model_lu_workspace(d, dtype)
+    _check(lib.model_lu_compose(*_lu_params(lp, up, log_s, sign_s, perm, d), d, dtype, _ptr(a_out), _ptr(workspace), _stream()))
+
+
+def model_lu_backward(g, lp, up, log_s, sign_s, perm, d, d_lp, d_up, d_log_s, workspace):
+    dtype = AE_BF16 if g.dtype == torch.bfloat16 else AE_F32
+    assert g.numel() == d * d and d_lp.numel() == d * d and d_up.numel() == d * d and d_log_s.numel() == d
+    assert workspace.numel() * workspace.element_size() >= model_lu_workspace(d, dtype)
+    _check(lib.model_lu_backward(_ptr(g), *_lu_params(lp, up, log_s, sign_s, perm, d), d, dtype, _ptr(d_lp, torch.float32),
+                                 _ptr(d_up, torch.float32), _ptr(d_log_s, torch.float32), _ptr(workspace), _stream()))
+
+
+def model_vol_penalty(log_s, d, value, d_log_s=None):
+    assert log_s.numel() == d and value.numel() == 1 and (d_log_s is None or d_log_s.numel() == d)
+    _check(lib.model_vol_penalty(_ptr(log_s, torch.float32), d, _ptr(value, torch.float32),
+                                 _ptr(d_log_s, torch.float32) if d_log_s is not None else _ptr(None), _stream()))
 
 
 def model_calibrate_mfma(lds_reads, random_data=0, iters=4000):

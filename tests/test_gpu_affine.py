@@ -1,0 +1,135 @@
+"""GPU parity of the LU parametrisation (model_lu_compose / model_lu_backward / model_vol_penalty) against
+oracle/affine_oracle.py, element by element, through the C boundary."""
+import ctypes as C
+
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import affine_oracle as ao
+
+pytestmark = pytest.mark.gpu
+
+# binary32 products against float64: 1e-4; bf16 operands and results (2^-9 relative each): 2e-2 — relative to the entry
+# plus the same fraction of the matrix's root mean square (entries are sums of d products of mixed sign)
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+@pytest.fixture(scope="module")
+def ae():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2602_17681_amd import binding
+    return binding
+
+
+def _close(got, ref, tol):
+    rms = float(np.sqrt(np.mean(ref ** 2))) + 1e-30
+    err = np.abs(got - ref) - tol * np.abs(ref)
+    return float(err.max()) <= tol * rms
+
+
+def _dev(ae, params):
+    import torch
+    lp, up, ls, sg, perm = params
+    return [torch.from_numpy(a).cuda() for a in (lp, up, ls, sg)] + [torch.from_numpy(perm).cuda()]
+
+
+def _round(a, dtype):
+    return wl.round_to_bf16(a.astype(np.float32)) if dtype == "bf16" else a.astype(np.float32)
+
+
+def _compose(ae, params, d, dtype):
+    import torch
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    a = torch.full((d, d), float("nan"), dtype=td, device="cuda")
+    ws = torch.empty(ae.model_lu_workspace(d, ae.DTYPES[dtype]), dtype=torch.uint8, device="cuda")
+    ae.model_lu_compose(*_dev(ae, params), d, a, ws)
+    torch.cuda.synchronize()
+    return a.float().cpu().numpy().astype(np.float64)
+
+
+def _backward(ae, g, params, d, dtype):
+    import torch
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    gt = torch.from_numpy(g.astype(np.float32)).cuda().to(td).contiguous()
+    dlp = torch.full((d, d), float("nan"), device="cuda")
+    dup = torch.full((d, d), float("nan"), device="cuda")
+    dls = torch.full((d,), float("nan"), device="cuda")
+    ws = torch.empty(ae.model_lu_workspace(d, ae.DTYPES[dtype]), dtype=torch.uint8, device="cuda")
+    ae.model_lu_backward(gt, *_dev(ae, params), d, dlp, dup, dls, ws)
+    torch.cuda.synchronize()
+    return [t.cpu().numpy().astype(np.float64) for t in (dlp, dup, dls)]
+
+
+CASES = [(32, "random"), (160, "random"), (512, "random"), (256, "bd_hadamard"), (1056, "random")]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("d,kind", CASES)
+def test_compose_matches_oracle(ae, d, kind, dtype):
+    params = wl.make_lu_params(d, seed=d, kind=kind, noise=1e-3 if kind == "bd_hadamard" else 0.0)
+    a = _compose(ae, params, d, dtype)
+    ref = ao.lu_compose(*params)
+    assert _close(a, ref, TOL[dtype]), np.abs(a - ref).max()
+    if kind == "bd_hadamard":                                         # the initialisation: block orthogonal up to the noise
+        assert np.abs(a @ a.T - np.eye(d)).max() < (0.05 if dtype == "bf16" else 0.02)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("d,kind", CASES)
+def test_backward_matches_oracle(ae, d, kind, dtype):
+    params = wl.make_lu_params(d, seed=d + 1, kind=kind, noise=1e-3 if kind == "bd_hadamard" else 0.0)
+    g = _round(np.random.default_rng(d).standard_normal((d, d)), dtype).astype(np.float64)
+    dlp, dup, dls = _backward(ae, g, params, d, dtype)
+    r_lp, r_up, r_ls = ao.lu_gradients(g, *params)
+    tol = TOL[dtype]
+    assert _close(dlp, r_lp, tol) and _close(dup, r_up, tol) and _close(dls, r_ls, tol)
+    assert np.array_equal(np.triu(dlp), np.zeros((d, d))) and np.array_equal(np.tril(dup), np.zeros((d, d)))
+
+
+def test_volume_penalty_matches_oracle(ae):
+    import torch
+    for d in (1, 32, 1000, 4096):
+        ls = (0.05 * np.random.default_rng(d).standard_normal(d)).astype(np.float32)
+        t = torch.from_numpy(ls).cuda()
+        val = torch.full((1,), float("nan"), device="cuda")
+        grad = torch.full((d,), float("nan"), device="cuda")
+        ae.model_vol_penalty(t, d, val, grad)
+        ae.model_vol_penalty(t, d, val)                                # the gradient is optional
+        v_o, g_o = ao.vol_penalty(ls)
+        assert abs(val.item() - v_o) <= 1e-6 * v_o + 1e-12
+        assert np.allclose(grad.cpu().numpy(), g_o, rtol=1e-6, atol=1e-9)
+    z = torch.zeros(64, device="cuda")
+    val = torch.ones(1, device="cuda")
+    ae.model_vol_penalty(z, 64, val)
+    assert val.item() == 0.0                                           # |s| = 1: no penalty
+
+
+def test_argument_checks(ae):
+    import torch
+    t = torch.zeros(64 * 64, device="cuda")
+    p = C.c_void_p(t.data_ptr())
+    n = C.c_int64()
+    assert ae.lib.model_lu_workspace(48, 0, C.byref(n)) == -1          # d not a multiple of 32
+    assert ae.lib.model_lu_workspace(64, 7, C.byref(n)) == -1          # dtype
+    assert ae.lib.model_lu_workspace(32768, 0, C.byref(n)) == -1       # too large
+    assert ae.lib.model_lu_workspace(64, 1, C.byref(n)) == 0 and n.value == 5 * 64 * 64 * 2
+    assert ae.lib.model_lu_compose(p, p, p, p, p, 48, 0, p, p, None) == -1
+    assert ae.lib.model_lu_compose(None, p, p, p, p, 64, 0, p, p, None) == -1
+    assert ae.lib.model_lu_backward(p, p, p, p, p, p, 64, 0, p, p, None, p, None) == -1
+    assert ae.lib.model_vol_penalty(p, 0, p, None, None) == -1
+    assert "model_vol_penalty" in ae.model_last_error()
+
+
+def test_full_size_compose_and_backward(ae):
+    """d = 4 096 in bf16, the launch bench.py times, every element against the oracle."""
+    d = 4096
+    params = wl.make_lu_params(d, seed=11, kind="bd_hadamard", noise=1e-3)
+    a = _compose(ae, params, d, "bf16")
+    assert _close(a, ao.lu_compose(*params), TOL["bf16"])
+    g = wl.round_to_bf16(np.random.default_rng(12).standard_normal((d, d)).astype(np.float32)).astype(np.float64)
+    dlp, dup, dls = _backward(ae, g, params, d, "bf16")
+    r_lp, r_up, r_ls = ao.lu_gradients(g, *params)
+    assert _close(dlp, r_lp, TOL["bf16"]) and _close(dup, r_up, TOL["bf16"]) and _close(dls, r_ls, TOL["bf16"])
