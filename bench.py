@@ -190,6 +190,9 @@ def bench_mx_quant(torch, ae, args):
     }
 
 
+# measured HBM bytes per launch of the triangular products (profiles/lu_param.md)
+LU_TRAFFIC_BYTES = {"bf16": 2.07e8}
+
 # measured HBM bytes per launch of the two GEMMs of the transformation error (profiles/transform_mse.md)
 TMSE_TRAFFIC_BYTES = {"bf16": 1.396e9}   # average of the two GEMM launches (1.301 GB and 1.491 GB)
 
@@ -255,6 +258,84 @@ def bench_transform_mse(torch, ae, args):
     }
 
 
+def bench_lu_param(torch, ae, args):
+    """One step = everything the LU parametrisation A = P L (U + diag s) of Eq. (4) costs per optimiser step for one
+    d x d matrix, d = 4 096: compose A from the free parameters, the volume regulariser and its gradient, and the
+    parameter gradients from dLoss/dA.  Algorithmic FLOPs: three products with a triangular factor of which (backward)
+    a triangle is wanted, 2 d^3 / 3 each."""
+    d = 4096
+    bf = args.dtype == "bf16"
+    td = torch.bfloat16 if bf else torch.float32
+    params = wl.make_lu_params(d, seed=11, kind="bd_hadamard", noise=1e-3)
+    lp, up, ls, sg = [torch.from_numpy(a).cuda() for a in params[:4]]
+    perm = torch.from_numpy(params[4]).cuda()
+    g_h = np.random.default_rng(12).standard_normal((d, d)).astype(np.float32)
+    g = torch.from_numpy(g_h).cuda().to(td).contiguous()
+    a = torch.empty((d, d), dtype=td, device="cuda")
+    dlp, dup = torch.empty((d, d), device="cuda"), torch.empty((d, d), device="cuda")
+    dls, vgrad, val = torch.empty(d, device="cuda"), torch.empty(d, device="cuda"), torch.empty(1, device="cuda")
+    ws = torch.empty(ae.model_lu_workspace(d, ae.DTYPES[args.dtype]), dtype=torch.uint8, device="cuda")
+
+    def step():
+        ae.model_lu_compose(lp, up, ls, sg, perm, d, a, ws)
+        ae.model_vol_penalty(ls, d, val, vgrad)
+        ae.model_lu_backward(g, lp, up, ls, sg, perm, d, dlp, dup, dls, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    step_ms = e0.elapsed_time(e1) / args.steps
+    # the three matrix-core products alone: HIP events around each launch inside the library
+    ae.model_lu_timing(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    gemm_ms, launches = ae.model_lu_timing(False)
+    avg_ms = gemm_ms / max(launches, 1)
+    flops = 2.0 * d ** 3                     # 3 x (2/3) d^3
+    ach = flops / 3.0 / avg_ms / 1e9
+    es = a.element_size()
+    from oracle import affine_oracle as ao
+    c0 = time.perf_counter()
+    reps = 0
+    while time.perf_counter() - c0 < (1.0 if args.no_cpu_baseline else 12.0):
+        ao.lu_compose(*params)
+        ao.vol_penalty(params[2])
+        ao.lu_gradients(g_h.astype(np.float64), *params)
+        reps += 1
+    ct = time.perf_counter() - c0
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = 1
+    return {
+        "metric": "matrices/sec, LU-parametrised 4096 x 4096 matrix: compose + regulariser + parameter gradients",
+        "value": args.steps / dt, "unit": "matrices/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": args.dtype, "data": "synthetic",
+        "config": {"workload": "lu_param: A = P L (U + diag s), d = 4096, block-Hadamard initialisation + noise", "d": d},
+        # the three GEMM launches of a step (62 % of its kernel time; twelve element-wise kernels are the rest)
+        "roofline": {"bound": "mfma", "kernel": "k_igemm (triangular K ranges)", "achieved": ach, "peak": PEAK[args.dtype],
+                     "unit": "TFLOP/s", "frac": ach / PEAK[args.dtype], "achieved_whole_step": flops / step_ms / 1e9,
+                     "traffic": LU_TRAFFIC_BYTES.get(args.dtype), "avg_ms": avg_ms, "launches_per_step": 3,
+                     "flops_per_launch": flops / 3, "bytes_per_launch": 3.0 * d * d * es, "step_ms_under_events": step_ms},
+        "cpu_baseline": {"value": reps / ct, "unit": "matrices/s", "cores": cores, "kind": "oracle",
+                         "sample": "%d full steps (d = 4096, float64) in %.1f s" % (reps, ct)},
+    }
+
+
 def cpu_baseline(name, budget_s=20.0):
     """The oracle as it stands, on a bounded sample of the same workload (same layer list and
     resolution, smaller batch), timed on this machine's host cores."""
@@ -307,6 +388,9 @@ def main():
     ap.add_argument("--transform-mse", action="store_true",
                     help="benchmark the transformation error E(T) of Eq. (2) (dense affine map, MX quantiser) on 16 384 tokens x "
                          "4 096 channels instead of a network: one JSON line with roofline and cpu_baseline")
+    ap.add_argument("--lu-param", action="store_true",
+                    help="benchmark the LU parametrisation of Eq. (4) (compose, regulariser, parameter gradients; d = 4096) "
+                         "instead of a network: one JSON line with roofline and cpu_baseline")
     ap.add_argument("--calibrate-mfma", action="store_true",
                     help="only run the library's plain matrix-core loop (with and without LDS fragment reads) and exit")
     ap.add_argument("--channel-sweep", action="store_true",
@@ -334,6 +418,9 @@ def main():
         return
     if args.transform_mse:
         print(json.dumps(bench_transform_mse(torch, ae, args)))
+        return
+    if args.lu_param:
+        print(json.dumps(bench_lu_param(torch, ae, args)))
         return
     if args.calibrate_mfma:
         res = {"kernel": "k_calib_mfma", "nominal_peak_tflops": PEAK["bf16"]}

@@ -214,7 +214,8 @@ int model_transform_mse(const void* x, const void* a_mat, const float* v, const 
  * 0..d-1 (an entry outside that range is treated as i; duplicates give unspecified rows, never an access out
  * of bounds).  dtype: storage type of the matrix operands and results (AE_F32 or AE_BF16); products run on the
  * matrix cores with binary32 accumulation.  d: a multiple of 32, 32..16384, else AE_EINVAL.  workspace:
- * model_lu_workspace bytes of device memory (the same size serves both calls).
+ * model_lu_workspace bytes of device memory (the same size serves both calls); the workspace and every [d][d]
+ * array must be 16-byte aligned.
  * model_lu_compose  writes a_out = A [d][d] in dtype.
  * model_lu_backward given g = dLoss/dA [d][d] in dtype, writes the gradients of the free parameters in binary32:
  *   d_lp [d][d] (strictly lower part, zero elsewhere), d_up [d][d] (strictly upper part, zero elsewhere),
@@ -228,6 +229,11 @@ int model_lu_backward(const void* g, const float* lp, const float* up, const flo
                       const int* perm, int64_t d, int dtype, float* d_lp, float* d_up, float* d_log_s,
                       void* workspace, void* stream);
 int model_vol_penalty(const float* log_s, int64_t d, float* value, float* d_log_s, void* stream);
+/* Measurement aid (not thread safe): returns in *gemm_ms / *launches (host, nullable) the time and count of the
+ * matrix-core products model_lu_compose / model_lu_backward launched since the last call, then clears both and
+ * switches the timing on (enable != 0) or off.  While it is on, every product is bracketed by HIP events on its
+ * stream and waited for, so the calls become synchronous. */
+int model_lu_timing(int enable, double* gemm_ms, int64_t* launches);
 
 /* Measurement aid: TFLOP/s of a loop of nothing but independent 32x32x16 bf16 matrix-core
  * instructions on every compute unit (two workgroups of four wavefronts each, two wavefronts per

@@ -23,7 +23,7 @@ SYMBOLS = [
     "model_set_sample_offset", "model_forward", "model_backward", "model_loss_mse", "model_noise",
     "model_pnorm_awgn", "model_gen_bits", "model_count_errors", "model_num_steps", "model_step_info",
     "model_get_activation", "model_timing_enable", "model_set_overlap", "model_calibrate_mfma", "model_mx_quantize", "model_transform_mse_workspace",
-    "model_transform_mse", "model_lu_workspace", "model_lu_compose", "model_lu_backward", "model_vol_penalty", "model_timing_slots",
+    "model_transform_mse", "model_lu_workspace", "model_lu_compose", "model_lu_backward", "model_vol_penalty", "model_lu_timing", "model_timing_slots",
     "model_timing_read", "model_timing_reset", "model_last_error",
 ]
 
@@ -67,6 +67,7 @@ def _load():
     L.model_lu_compose.argtypes = [vp, vp, vp, vp, vp, C.c_int64, C.c_int, vp, vp, vp]
     L.model_lu_backward.argtypes = [vp, vp, vp, vp, vp, vp, C.c_int64, C.c_int, vp, vp, vp, vp, vp]
     L.model_vol_penalty.argtypes = [vp, C.c_int64, vp, vp, vp]
+    L.model_lu_timing.argtypes = [C.c_int, C.POINTER(C.c_double), i64p]
     L.model_timing_slots.argtypes = [vp, C.POINTER(C.c_int)]
     L.model_timing_read.argtypes = [vp, C.c_int, C.c_char_p, C.c_int, C.POINTER(C.c_double), i64p,
                                     C.POINTER(C.c_double), C.POINTER(C.c_double)]
@@ -271,6 +272,13 @@ def model_vol_penalty(log_s, d, value, d_log_s=None):
     assert log_s.numel() == d and value.numel() == 1 and (d_log_s is None or d_log_s.numel() == d)
     _check(lib.model_vol_penalty(_ptr(log_s, torch.float32), d, _ptr(value, torch.float32),
                                  _ptr(d_log_s, torch.float32) if d_log_s is not None else _ptr(None), _stream()))
+
+
+def model_lu_timing(enable):
+    """(milliseconds, launches) of the matrix-core products since the last call; then timing on / off."""
+    ms, n = C.c_double(0.0), C.c_int64(0)
+    _check(lib.model_lu_timing(1 if enable else 0, C.byref(ms), C.byref(n)))
+    return ms.value, n.value
 
 
 def model_calibrate_mfma(lds_reads, random_data=0, iters=4000):

@@ -7,8 +7,12 @@
 // The three d x d x d products run on the matrix cores through the dense case of the implicit-GEMM kernel
 // (y[m][n] = sum_k x[m][k] w[n][k], operands in the storage type, binary32 accumulation); small element-wise
 // kernels materialise the triangular operands from the binary32 master parameters (transposed where the product
-// needs it) and cut the products back to the triangles the parameters live on.
+// needs it), apply the permutation to rows (of L (U + diag s) forward, of G backward), and cut the products back
+// to the triangles the parameters live on.  Every product has a triangular operand and, backward, only a triangle
+// of the result is wanted: the GEMM kernel walks only the K range of each tile that can hold non-zeros and skips
+// the tiles nobody reads — a third of the multiply-adds of three dense products.
 #include <hip/hip_runtime.h>
+#include <stdint.h>
 #include <string.h>
 
 #include "ae_device.h"
@@ -18,21 +22,68 @@ namespace ae {
 namespace {
 
 struct LuSrc {
-  const float* lp; const float* up; const float* log_s; const float* sign; const int* perm; const void* g;
+  const float* lp; const float* up; const float* log_s; const float* sign; const int* inv_perm; const void* g;
   int d;
 };
-enum { LU_PL = 0, LU_UD = 1, LU_G = 2 };
+enum { LU_L = 0, LU_UD = 1, LU_B = 2 };
 
-// entry (r, c) of P L, of U + diag(s), or of G
+// entry (r, c) of L, of U + diag(s), or of B = P^T G (row r of B is row inv_perm[r] of G)
 template <typename T, int SRC>
 __device__ __forceinline__ float lu_elem(const LuSrc& q, int r, int c) {
-  if (SRC == LU_PL) {
-    int row = q.perm[r];
-    if ((unsigned)row >= (unsigned)q.d) row = r;                       // not a permutation: stay inside the arrays
-    return c < row ? q.lp[(int64_t)row * q.d + c] : (c == row ? 1.0f : 0.0f);
-  }
+  if (SRC == LU_L) return c < r ? q.lp[(int64_t)r * q.d + c] : (c == r ? 1.0f : 0.0f);
   if (SRC == LU_UD) return r < c ? q.up[(int64_t)r * q.d + c] : (r == c ? q.sign[c] * expf(q.log_s[c]) : 0.0f);
-  return Store<T>::ld(reinterpret_cast<const T*>(q.g) + (int64_t)r * q.d + c);
+  return Store<T>::ld(reinterpret_cast<const T*>(q.g) + (int64_t)q.inv_perm[r] * q.d + c);
+}
+
+// eight consecutive entries of one row, to and from the storage type
+template <typename T> __device__ __forceinline__ void load8(const T* p, float (&v)[8]);
+template <> __device__ __forceinline__ void load8<bf16_t>(const bf16_t* p, float (&v)[8]) { Store<bf16_t>::ldv(p, v); }
+template <> __device__ __forceinline__ void load8<float>(const float* p, float (&v)[8]) {
+  const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+template <typename T> __device__ __forceinline__ void store8(T* p, const float (&v)[8]);
+template <> __device__ __forceinline__ void store8<bf16_t>(bf16_t* p, const float (&v)[8]) { Store<bf16_t>::stv(p, v); }
+template <> __device__ __forceinline__ void store8<float>(float* p, const float (&v)[8]) {
+  *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+  *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+}
+
+// out = the transpose of the matrix SRC in the storage type: 64 x 64 tiles through LDS, eight entries per lane on both
+// sides; source chunks that lie wholly in the zero triangle read nothing.  d % 64 == 0.
+template <typename T, int SRC>
+__global__ __launch_bounds__(256) void k_lu_build_transposed(LuSrc q, T* __restrict__ out) {
+  __shared__ float tile[64][65];
+  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;           // output tile: rows r0.., columns c0..
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int chunk = threadIdx.x + 256 * j;
+    const int sr = c0 + (chunk >> 3), sc0 = r0 + ((chunk & 7) << 3);   // source row (an output column), first source column
+    float v[8];
+    if (SRC == LU_B) {
+      load8<T>(reinterpret_cast<const T*>(q.g) + (int64_t)q.inv_perm[sr] * q.d + sc0, v);
+    } else if (SRC == LU_L ? sc0 + 7 < sr : sc0 > sr) {
+      load8<float>((SRC == LU_L ? q.lp : q.up) + (int64_t)sr * q.d + sc0, v);
+    } else if (SRC == LU_L ? sc0 > sr : sc0 + 7 < sr) {
+#pragma unroll
+      for (int t = 0; t < 8; ++t) v[t] = 0.0f;
+    } else {
+#pragma unroll
+      for (int t = 0; t < 8; ++t) v[t] = lu_elem<T, SRC>(q, sr, sc0 + t);
+    }
+#pragma unroll
+    for (int t = 0; t < 8; ++t) tile[chunk >> 3][((chunk & 7) << 3) + t] = v[t];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int chunk = threadIdx.x + 256 * j;
+    const int orow = chunk >> 3, oc0 = (chunk & 7) << 3;           // output row r0 + orow, columns c0 + oc0 ..
+    float v[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) v[t] = tile[oc0 + t][orow];
+    store8<T>(out + (int64_t)(r0 + orow) * q.d + c0 + oc0, v);
+  }
 }
 
 // out = the matrix SRC (TR = false) or its transpose (TR = true), in the storage type; 32 x 32 tiles, d % 32 == 0
@@ -56,30 +107,95 @@ __global__ __launch_bounds__(256) void k_lu_build(LuSrc q, T* __restrict__ out) 
   }
 }
 
-// d/dU = strictly upper part of L^T P^T G, d/dlog_s = its diagonal times s
+// out = the matrix SRC, row by row, eight entries per lane; chunks that lie wholly in the zero triangle read nothing
+template <typename T, int SRC>
+__global__ __launch_bounds__(256) void k_lu_build_rows(LuSrc q, T* __restrict__ out) {
+  const int cpr = q.d >> 3;
+  const int64_t n = (int64_t)q.d * cpr;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const int r = (int)(i / cpr), c0 = (int)(i - (int64_t)r * cpr) << 3;
+    float v[8];
+    if (SRC == LU_B) {
+      load8<T>(reinterpret_cast<const T*>(q.g) + (int64_t)q.inv_perm[r] * q.d + c0, v);
+    } else if (SRC == LU_L ? c0 + 7 < r : c0 > r) {
+      load8<float>((SRC == LU_L ? q.lp : q.up) + (int64_t)r * q.d + c0, v);       // wholly inside the used triangle
+    } else if (SRC == LU_L ? c0 > r : c0 + 7 < r) {
+#pragma unroll
+      for (int t = 0; t < 8; ++t) v[t] = 0.0f;
+    } else {
+#pragma unroll
+      for (int t = 0; t < 8; ++t) v[t] = lu_elem<T, SRC>(q, r, c0 + t);           // the chunk that holds the diagonal
+    }
+    store8<T>(out + (int64_t)r * q.d + c0, v);
+  }
+}
+
+// inv[i] = i, then inv[perm[i]] = i (two launches): entries of perm outside 0..d-1 are ignored, so every inv[r]
+// stays inside 0..d-1 whatever perm holds
+__global__ void k_lu_iota(int* __restrict__ inv, int d) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < d) inv[i] = i;
+}
+__global__ void k_lu_invert_perm(const int* __restrict__ perm, int* __restrict__ inv, int d) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < d && (unsigned)perm[i] < (unsigned)d) inv[perm[i]] = i;
+}
+
+// A[i][:] = Y[perm[i]][:], 16 bytes per lane (row bytes are a multiple of 64)
+__global__ __launch_bounds__(256) void k_lu_permute_rows(const uint4* __restrict__ y, const int* __restrict__ perm, int d,
+                                                         int chunks_per_row, uint4* __restrict__ a) {
+  const int64_t n = (int64_t)d * chunks_per_row;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const int r = (int)(i / chunks_per_row), c = (int)(i - (int64_t)r * chunks_per_row);
+    int src = perm[r];
+    if ((unsigned)src >= (unsigned)d) src = r;                        // not a permutation: stay inside the arrays
+    a[i] = y[(int64_t)src * chunks_per_row + c];
+  }
+}
+
+// d/dU = strictly upper part of L^T B, d/dlog_s = its diagonal times s  (tiles below the diagonal were never written:
+// chunks wholly below it are not read)
 template <typename T>
 __global__ __launch_bounds__(256) void k_lu_grad_upper(const T* __restrict__ dud, const float* __restrict__ log_s,
                                                        const float* __restrict__ sign, int d, float* __restrict__ dup,
                                                        float* __restrict__ dlog_s) {
-  const int64_t n = (int64_t)d * d;
+  const int cpr = d >> 3;
+  const int64_t n = (int64_t)d * cpr;
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
-    const int k = (int)(i / d), c = (int)(i - (int64_t)k * d);
-    const float v = Store<T>::ld(dud + i);
-    dup[i] = c > k ? v : 0.0f;
-    if (c == k) dlog_s[k] = v * (sign[k] * expf(log_s[k]));
+    const int k = (int)(i / cpr), c0 = (int)(i - (int64_t)k * cpr) << 3;
+    float v[8];
+    if (c0 + 7 >= k) {
+      load8<T>(dud + (int64_t)k * d + c0, v);
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        if (c0 + t == k) dlog_s[k] = v[t] * (sign[k] * expf(log_s[k]));
+        if (c0 + t <= k) v[t] = 0.0f;
+      }
+    } else {
+#pragma unroll
+      for (int t = 0; t < 8; ++t) v[t] = 0.0f;
+    }
+    store8<float>(dup + (int64_t)k * d + c0, v);
   }
 }
 
-// d/dL: row i of G (U + diag s)^T belongs to row perm[i] of L; strictly lower part only
+// d/dL = strictly lower part of B (U + diag s)^T  (tiles above the diagonal were never written: not read)
 template <typename T>
-__global__ __launch_bounds__(256) void k_lu_grad_lower(const T* __restrict__ dpl, const int* __restrict__ perm, int d,
-                                                       float* __restrict__ dlp) {
-  const int64_t n = (int64_t)d * d;
+__global__ __launch_bounds__(256) void k_lu_grad_lower(const T* __restrict__ dl, int d, float* __restrict__ dlp) {
+  const int cpr = d >> 3;
+  const int64_t n = (int64_t)d * cpr;
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
-    const int r = (int)(i / d), c = (int)(i - (int64_t)r * d);
-    int row = perm[r];
-    if ((unsigned)row >= (unsigned)d) row = r;
-    dlp[(int64_t)row * d + c] = c < row ? Store<T>::ld(dpl + i) : 0.0f;
+    const int r = (int)(i / cpr), c0 = (int)(i - (int64_t)r * cpr) << 3;
+    float v[8];
+    if (c0 < r) {
+      load8<T>(dl + (int64_t)r * d + c0, v);
+#pragma unroll
+      for (int t = 0; t < 8; ++t) if (c0 + t >= r) v[t] = 0.0f;
+    } else {
+#pragma unroll
+      for (int t = 0; t < 8; ++t) v[t] = 0.0f;
+    }
+    store8<float>(dlp + (int64_t)r * d + c0, v);
   }
 }
 
@@ -101,13 +217,47 @@ void launch_build(const LuSrc& q, void* out, hipStream_t s) {
   hipLaunchKernelGGL((k_lu_build<T, SRC, TR>), dim3(q.d / 32, q.d / 32), dim3(256), 0, s, q, reinterpret_cast<T*>(out));
 }
 
-// y[m][n] = sum_k x[m][k] w[n][k], all d x d in the storage type
-int dense_product(const void* x, const void* w, void* y, int d, int dtype, hipStream_t s) {
+template <typename T, int SRC>
+void launch_build_transposed(const LuSrc& q, void* out, hipStream_t s) {
+  if (q.d % 64 == 0) hipLaunchKernelGGL((k_lu_build_transposed<T, SRC>), dim3(q.d / 64, q.d / 64), dim3(256), 0, s, q, reinterpret_cast<T*>(out));
+  else launch_build<T, SRC, true>(q, out, s);
+}
+
+template <typename T, int SRC>
+void launch_build_rows(const LuSrc& q, void* out, hipStream_t s) {
+  const int64_t g = ((int64_t)q.d * (q.d / 8) + 255) / 256;
+  hipLaunchKernelGGL((k_lu_build_rows<T, SRC>), dim3((unsigned)(g < 8192 ? g : 8192)), dim3(256), 0, s, q, reinterpret_cast<T*>(out));
+}
+
+// measurement aid (model_lu_timing): HIP events around every matrix-core product, waited for at once
+bool g_timing = false;
+double g_timing_ms = 0.0;
+int64_t g_timing_launches = 0;
+hipEvent_t g_ev0 = nullptr, g_ev1 = nullptr;
+
+// y[m][n] = sum_k x[m][k] w[n][k], all d x d in the storage type; tri: which operand is triangular (CONV_TRI_*)
+int dense_product(const void* x, const void* w, void* y, int d, int dtype, int tri, hipStream_t s) {
   ConvArgs a;
   memset(&a, 0, sizeof(a));
   a.x = x; a.w = w; a.bias = nullptr; a.y = y;
   a.n = d; a.hc = a.wc = 1; a.cin = a.cout = d; a.k = 1; a.up = 0; a.act = ACT_NONE; a.dtype = dtype;
-  return launch_conv_mfma(a, s);
+  a.tri = tri;
+  if (!g_timing) return launch_conv_mfma(a, s);
+  AE_HIP(hipEventRecord(g_ev0, s));
+  AE_TRY(launch_conv_mfma(a, s));
+  AE_HIP(hipEventRecord(g_ev1, s));
+  AE_HIP(hipEventSynchronize(g_ev1));
+  float ms = 0.0f;
+  AE_HIP(hipEventElapsedTime(&ms, g_ev0, g_ev1));
+  g_timing_ms += ms;
+  ++g_timing_launches;
+  return AE_OK;
+}
+
+int64_t lu_mat_bytes(int64_t d, int dtype) { return d * d * (int64_t)dtype_size(dtype); }
+unsigned lu_grid(int64_t items) {
+  const int64_t g = (items + 256 * 8 - 1) / (256 * 8);
+  return (unsigned)(g < 4096 ? (g < 1 ? 1 : g) : 4096);
 }
 
 int check_lu_size(const char* who, int64_t d, int dtype) {
@@ -123,7 +273,7 @@ extern "C" int model_lu_workspace(int64_t d, int dtype, int64_t* bytes) {
   using namespace ae;
   if (!bytes) return fail(AE_EINVAL, "model_lu_workspace: null argument");
   AE_TRY(check_lu_size("model_lu_workspace", d, dtype));
-  *bytes = 5 * d * d * (int64_t)dtype_size(dtype);
+  *bytes = 6 * lu_mat_bytes(d, dtype) + ((d * 4 + 255) / 256) * 256;
   return AE_OK;
 }
 
@@ -132,16 +282,23 @@ extern "C" int model_lu_compose(const float* lp, const float* up, const float* l
   using namespace ae;
   if (!lp || !up || !log_s || !sign_s || !perm || !a_out || !workspace) return fail(AE_EINVAL, "model_lu_compose: null argument");
   AE_TRY(check_lu_size("model_lu_compose", d, dtype));
+  if (((reinterpret_cast<uintptr_t>(a_out) | reinterpret_cast<uintptr_t>(workspace) | reinterpret_cast<uintptr_t>(lp) |
+        reinterpret_cast<uintptr_t>(up)) & 15) != 0)
+    return fail(AE_EINVAL, "model_lu_compose: the matrices and the workspace must be 16-byte aligned");
   hipStream_t s = (hipStream_t)stream;
-  const int64_t mat = d * d * (int64_t)dtype_size(dtype);
+  const int64_t mat = lu_mat_bytes(d, dtype);
   char* ws = reinterpret_cast<char*>(workspace);
-  void* pl = ws;                // P L               [i][k]
+  void* l = ws;                 // L                 [i][k]
   void* udt = ws + mat;         // (U + diag s)^T    [n][k]
-  LuSrc q{lp, up, log_s, sign_s, perm, nullptr, (int)d};
-  if (dtype == AE_BF16) { launch_build<bf16_t, LU_PL, false>(q, pl, s); launch_build<bf16_t, LU_UD, true>(q, udt, s); }
-  else { launch_build<float, LU_PL, false>(q, pl, s); launch_build<float, LU_UD, true>(q, udt, s); }
+  void* y = ws + 2 * mat;       // L (U + diag s)    [i][n]
+  LuSrc q{lp, up, log_s, sign_s, nullptr, nullptr, (int)d};
+  if (dtype == AE_BF16) { launch_build_rows<bf16_t, LU_L>(q, l, s); launch_build_transposed<bf16_t, LU_UD>(q, udt, s); }
+  else { launch_build_rows<float, LU_L>(q, l, s); launch_build_transposed<float, LU_UD>(q, udt, s); }
   AE_TRY(launch_status("lu_build"));
-  return dense_product(pl, udt, a_out, (int)d, dtype, s);
+  AE_TRY(dense_product(l, udt, y, (int)d, dtype, CONV_TRI_LOWER_UPPER, s));
+  const int cpr = (int)(d * (int64_t)dtype_size(dtype) / 16);
+  hipLaunchKernelGGL(k_lu_permute_rows, dim3(lu_grid(d * cpr)), dim3(256), 0, s, (const uint4*)y, perm, (int)d, cpr, (uint4*)a_out);
+  return launch_status("lu_permute_rows");
 }
 
 extern "C" int model_lu_backward(const void* g, const float* lp, const float* up, const float* log_s, const float* sign_s,
@@ -151,33 +308,56 @@ extern "C" int model_lu_backward(const void* g, const float* lp, const float* up
   if (!g || !lp || !up || !log_s || !sign_s || !perm || !d_lp || !d_up || !d_log_s || !workspace)
     return fail(AE_EINVAL, "model_lu_backward: null argument");
   AE_TRY(check_lu_size("model_lu_backward", d, dtype));
+  if (((reinterpret_cast<uintptr_t>(g) | reinterpret_cast<uintptr_t>(workspace) | reinterpret_cast<uintptr_t>(lp) |
+        reinterpret_cast<uintptr_t>(up) | reinterpret_cast<uintptr_t>(d_lp) | reinterpret_cast<uintptr_t>(d_up)) & 15) != 0)
+    return fail(AE_EINVAL, "model_lu_backward: the matrices and the workspace must be 16-byte aligned");
   hipStream_t s = (hipStream_t)stream;
-  const int64_t mat = d * d * (int64_t)dtype_size(dtype);
+  const int64_t mat = lu_mat_bytes(d, dtype);
   char* ws = reinterpret_cast<char*>(workspace);
-  void* plt = ws;               // (P L)^T           [k][i]
-  void* gt = ws + mat;          // G^T               [n][i]
+  void* lt = ws;                // L^T               [k][i]
+  void* bt = ws + mat;          // B^T = (P^T G)^T   [n][i]
   void* ud = ws + 2 * mat;      // U + diag s        [k][n]
-  void* dud = ws + 3 * mat;     // (P L)^T G         [k][n]
-  void* dpl = ws + 4 * mat;     // G (U + diag s)^T  [i][k]
-  LuSrc q{lp, up, log_s, sign_s, perm, g, (int)d};
+  void* b = ws + 3 * mat;       // B = P^T G         [r][n]
+  void* dud = ws + 4 * mat;     // L^T B             [k][n]  (on and above the diagonal)
+  void* dl = ws + 5 * mat;      // B (U + diag s)^T  [r][k]  (below the diagonal)
+  int* inv = reinterpret_cast<int*>(ws + 6 * mat);
+  const unsigned pg = (unsigned)((d + 255) / 256);
+  hipLaunchKernelGGL(k_lu_iota, dim3(pg), dim3(256), 0, s, inv, (int)d);
+  hipLaunchKernelGGL(k_lu_invert_perm, dim3(pg), dim3(256), 0, s, perm, inv, (int)d);
+  LuSrc q{lp, up, log_s, sign_s, inv, g, (int)d};
   if (dtype == AE_BF16) {
-    launch_build<bf16_t, LU_PL, true>(q, plt, s); launch_build<bf16_t, LU_G, true>(q, gt, s); launch_build<bf16_t, LU_UD, false>(q, ud, s);
+    launch_build_transposed<bf16_t, LU_L>(q, lt, s); launch_build_transposed<bf16_t, LU_B>(q, bt, s);
+    launch_build_rows<bf16_t, LU_UD>(q, ud, s); launch_build_rows<bf16_t, LU_B>(q, b, s);
   } else {
-    launch_build<float, LU_PL, true>(q, plt, s); launch_build<float, LU_G, true>(q, gt, s); launch_build<float, LU_UD, false>(q, ud, s);
+    launch_build_transposed<float, LU_L>(q, lt, s); launch_build_transposed<float, LU_B>(q, bt, s);
+    launch_build_rows<float, LU_UD>(q, ud, s); launch_build_rows<float, LU_B>(q, b, s);
   }
   AE_TRY(launch_status("lu_build"));
-  AE_TRY(dense_product(plt, gt, dud, (int)d, dtype, s));
-  AE_TRY(dense_product(g, ud, dpl, (int)d, dtype, s));
-  const int64_t n = d * d;
-  const unsigned grid = (unsigned)((n + 256 * 8 - 1) / (256 * 8) < 4096 ? (n + 256 * 8 - 1) / (256 * 8) : 4096);
+  AE_TRY(dense_product(lt, bt, dud, (int)d, dtype, CONV_TRI_UPPER_X, s));
+  AE_TRY(dense_product(b, ud, dl, (int)d, dtype, CONV_TRI_UPPER_W, s));
+  const unsigned grid = lu_grid(d * d / 8 * 4);
   if (dtype == AE_BF16) {
     hipLaunchKernelGGL((k_lu_grad_upper<bf16_t>), dim3(grid), dim3(256), 0, s, (const bf16_t*)dud, log_s, sign_s, (int)d, d_up, d_log_s);
-    hipLaunchKernelGGL((k_lu_grad_lower<bf16_t>), dim3(grid), dim3(256), 0, s, (const bf16_t*)dpl, perm, (int)d, d_lp);
+    hipLaunchKernelGGL((k_lu_grad_lower<bf16_t>), dim3(grid), dim3(256), 0, s, (const bf16_t*)dl, (int)d, d_lp);
   } else {
     hipLaunchKernelGGL((k_lu_grad_upper<float>), dim3(grid), dim3(256), 0, s, (const float*)dud, log_s, sign_s, (int)d, d_up, d_log_s);
-    hipLaunchKernelGGL((k_lu_grad_lower<float>), dim3(grid), dim3(256), 0, s, (const float*)dpl, perm, (int)d, d_lp);
+    hipLaunchKernelGGL((k_lu_grad_lower<float>), dim3(grid), dim3(256), 0, s, (const float*)dl, (int)d, d_lp);
   }
   return launch_status("lu_backward");
+}
+
+extern "C" int model_lu_timing(int enable, double* gemm_ms, int64_t* launches) {
+  using namespace ae;
+  if (gemm_ms) *gemm_ms = g_timing_ms;
+  if (launches) *launches = g_timing_launches;
+  if (enable && !g_ev0) {
+    AE_HIP(hipEventCreate(&g_ev0));
+    AE_HIP(hipEventCreate(&g_ev1));
+  }
+  g_timing = enable != 0;
+  g_timing_ms = 0.0;
+  g_timing_launches = 0;
+  return AE_OK;
 }
 
 extern "C" int model_vol_penalty(const float* log_s, int64_t d, float* value, float* d_log_s, void* stream) {

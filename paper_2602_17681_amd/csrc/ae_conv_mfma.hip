@@ -56,6 +56,11 @@ struct IgemmParams {
   //   2: nothing is stored; the epilogue forms resid[m][n] - (acc + bias) and leaves per-tile column sums of it
   //      and of its square in `partial` (resid: [M][N] in the storage type)
   const void* resid;
+  // Square dense products (M = N = K) with triangular operands: K range per tile, and tiles nobody wants skipped.
+  //   1: x[m][k] = 0 for k > m and w[n][k] = 0 for k > n (lower times upper): K ends at min(last row, last column) + 1
+  //   2: x[m][k] = 0 for k < m, wanted outputs n >= m: K starts at the tile's first row; tiles below the diagonal return
+  //   3: w[n][k] = 0 for k < n, wanted outputs n < m: K starts at the tile's first column; tiles above the diagonal return
+  int tri;
 };
 
 // output row (pixel index in y) of GEMM row m
@@ -392,6 +397,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
   int lb0 = xcd_logical_block((int)blockIdx.x, (int)gridDim.x);
+  // triangular products: tile rows differ in work by an order of magnitude, so neighbouring tiles go to different
+  // XCDs (the hardware's own round-robin) instead of one contiguous range per XCD, the longest K ranges first
+  if (p.tri != 0) lb0 = p.tri == 1 ? (int)gridDim.x - 1 - (int)blockIdx.x : (int)blockIdx.x;
   int phase = 0;
   if (p.phases == 4) { phase = lb0 & 3; lb0 >>= 2; }   // the four phases of a tile run side by side: they read the same input
   const int split = INTERIOR ? 0 : lb0 / p.tiles_mn;
@@ -401,8 +409,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   constexpr int kGroupM = 4;
   const int gsz = kGroupM * p.tiles_n, grp = lb / gsz, in_grp = lb - grp * gsz;
   const int gm = min(p.tiles_mn / p.tiles_n - grp * kGroupM, kGroupM);
-  const int tile_n = in_grp / gm;
-  const int64_t tile_m = grp * kGroupM + in_grp % gm;
+  int tile_n = in_grp / gm;
+  int64_t tile_m = grp * kGroupM + in_grp % gm;
+  if (p.tri == 3) {                             // K range [column, K): walk column by column, the longest first
+    const int tiles_m = p.tiles_mn / p.tiles_n;
+    tile_n = lb / tiles_m;
+    tile_m = lb - tile_n * tiles_m;
+  }
   const int64_t m0 = tile_m * BM;
   const int n0 = tile_n * BN;
   const int pad_h = p.pad - (phase >> 1), pad_w = p.pad - (phase & 1);
@@ -435,7 +448,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
     b_off[i] = row < p.N ? (unsigned)(phase * p.N + row) * (unsigned)p.K * (unsigned)ES + (unsigned)gchunk * 16u : kOob;
   }
 
-  const int kt0 = INTERIOR ? 0 : split * p.slabs_per_split;             // first K slab of this workgroup
+  int k_lo = 0, k_hi = p.K;                                             // triangular operands: see IgemmParams::tri
+  if (p.tri == 1) k_hi = (int)min((int64_t)p.K, min(m0 + BM, (int64_t)n0 + BN));
+  else if (p.tri == 2) { if ((int64_t)n0 + BN <= m0) return; k_lo = (int)m0; }
+  else if (p.tri == 3) { if ((int64_t)n0 >= m0 + BM) return; k_lo = n0; }
+  const int kt_lo = k_lo / BK, kt_hi = (k_hi + BK - 1) / BK;
+  const int kt0 = INTERIOR ? kt_lo : max(kt_lo, split * p.slabs_per_split);   // first K slab of this workgroup
   int rs = (kt0 * BK) / p.Cin, ci0 = (kt0 * BK) % p.Cin;                // filter tap and first channel of the next slab to load
   unsigned kbyte = (unsigned)(kt0 * BKB);       // byte offset of the next slab inside a weight row
 #define IGEMM_TAP()                                                                                          \
@@ -495,7 +513,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-  const int KT = INTERIOR ? p.K / BK : min(p.K / BK - kt0, p.slabs_per_split);
+  const int KT = INTERIOR ? kt_hi - kt0 : min(kt_hi - kt0, p.slabs_per_split);   // (tri launches have one split)
   if (ci0 != 0) IGEMM_TAP();                     // a split that starts inside a tap (the loaders compute a tap's offsets at its first slab)
   if constexpr (DMA) {
     constexpr int L = A_CHUNKS + B_CHUNKS;       // loads per thread and slab
@@ -945,6 +963,10 @@ int launch_conv_mfma(const ConvArgs& a0, hipStream_t s) {
   p.Hc = a.hc; p.Wc = a.wc; p.Cin = a.cin; p.ksz = a.k; p.up = a.up; p.act = a.act;
   p.Hv = a.hc; p.Wv = a.wc; p.stride = 1; p.pad = (a.k - 1) >> 1; p.phases = 1;
   p.resid = a0.resid;
+  p.tri = a0.tri;
+  if (a0.tri != 0 && (a0.tri < 0 || a0.tri > 3 || a.k != 1 || a.hc != 1 || a.wc != 1 || a.up != 0 || a.n != a.cout || a.cin != a.cout ||
+                      a0.epi != CONV_EPI_NONE || a.partial))
+    return fail(AE_EINVAL, "conv_mfma: triangular K ranges are for square dense products only");
   p.x_bytes = (unsigned)((int64_t)a.n * (a.hc >> a.up) * (a.wc >> a.up) * a.cin * es);
   p.w_bytes = (unsigned)((int64_t)a.cout * a.k * a.k * a.cin * es);
   if (a0.geom == CONV_UP_PHASES) {
@@ -981,6 +1003,7 @@ int launch_conv_mfma(const ConvArgs& a0, hipStream_t s) {
   const int KT = (int)((int64_t)p.K * es / t.bkb);
   int splits = conv_mfma_splits(a0);
   if (splits > 1 && (!a.splitk_ws || (int64_t)splits * p.M * p.N > a.splitk_floats)) splits = 1;
+  if (a0.tri != 0) splits = 1;
   p.tiles_mn = (int)(tiles_m * p.tiles_n);
   p.slabs_per_split = (KT + splits - 1) / splits;
   splits = (KT + p.slabs_per_split - 1) / p.slabs_per_split;

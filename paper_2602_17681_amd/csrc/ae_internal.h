@@ -145,7 +145,14 @@ struct ConvArgs {
   //                   resid - (x w^T + bias) and of its square (resid: [rows][cout] in the storage type).
   int epi = 0;
   const void* resid = nullptr;
+  // Square dense products (n = cin = cout, k = 1) with triangular operands; the kernel then walks only the K range
+  // that can hold non-zeros and returns at once in tiles that hold no wanted output (they are left unwritten):
+  //   CONV_TRI_LOWER_UPPER  x lower triangular, w^T upper triangular (w[n][k] = 0 for k > n);
+  //   CONV_TRI_UPPER_X      x upper triangular; wanted: the outputs on and above the diagonal;
+  //   CONV_TRI_UPPER_W      w upper triangular (w[n][k] = 0 for k < n); wanted: the outputs below the diagonal.
+  int tri = 0;
 };
+enum { CONV_TRI_NONE = 0, CONV_TRI_LOWER_UPPER = 1, CONV_TRI_UPPER_X = 2, CONV_TRI_UPPER_W = 3 };
 enum { CONV_PLAIN = 0, CONV_UP_PHASES = 1, CONV_UP_DGRAD = 2 };
 enum { CONV_EPI_NONE = 0, CONV_EPI_MXQ = 1, CONV_EPI_RESID = 2 };
 bool conv_epi_usable(const ConvArgs& a);         // can launch_conv_mfma run a.epi for this shape?

@@ -115,12 +115,25 @@ def test_argument_checks(ae):
     assert ae.lib.model_lu_workspace(48, 0, C.byref(n)) == -1          # d not a multiple of 32
     assert ae.lib.model_lu_workspace(64, 7, C.byref(n)) == -1          # dtype
     assert ae.lib.model_lu_workspace(32768, 0, C.byref(n)) == -1       # too large
-    assert ae.lib.model_lu_workspace(64, 1, C.byref(n)) == 0 and n.value == 5 * 64 * 64 * 2
+    assert ae.lib.model_lu_workspace(64, 1, C.byref(n)) == 0 and n.value == 6 * 64 * 64 * 2 + 256
     assert ae.lib.model_lu_compose(p, p, p, p, p, 48, 0, p, p, None) == -1
     assert ae.lib.model_lu_compose(None, p, p, p, p, 64, 0, p, p, None) == -1
     assert ae.lib.model_lu_backward(p, p, p, p, p, p, 64, 0, p, p, None, p, None) == -1
     assert ae.lib.model_vol_penalty(p, 0, p, None, None) == -1
     assert "model_vol_penalty" in ae.model_last_error()
+
+
+def test_product_timing_counts_launches_and_changes_nothing(ae):
+    d = 256
+    params = wl.make_lu_params(d, seed=3)
+    a0 = _compose(ae, params, d, "bf16")
+    ae.model_lu_timing(True)
+    a1 = _compose(ae, params, d, "bf16")
+    g = wl.round_to_bf16(np.random.default_rng(1).standard_normal((d, d)).astype(np.float32)).astype(np.float64)
+    _backward(ae, g, params, d, "bf16")
+    ms, n = ae.model_lu_timing(False)
+    assert n == 3 and 0.0 < ms < 100.0 and np.array_equal(a0, a1)
+    assert ae.model_lu_timing(False) == (0.0, 0)
 
 
 def test_full_size_compose_and_backward(ae):
