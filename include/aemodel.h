@@ -235,6 +235,25 @@ int model_vol_penalty(const float* log_s, int64_t d, float* value, float* d_log_
  * stream and waited for, so the calls become synchronous. */
 int model_lu_timing(int enable, double* gemm_ms, int64_t* launches);
 
+/* Folding of affine transformations T(x) = A x + v into a linear layer f(x) = W x + b (the paper's appendix
+ * "Folding & Transformation Structure"): the layer x -> T_l(f(T_r^-1(x))) has
+ *     w_out = A_l W A_r^-1 ,   b_out = A_l b - w_out v_r + v_l .
+ * w, w_out: [out][in] row-major in dtype (AE_F32 / AE_BF16), device, distinct; b (nullable = zero), b_out: binary32
+ * [out].  a_left (nullable): [p][p] in dtype, applied to every group of p output features (p divides out; p = out:
+ * one matrix for the whole side), v_left (nullable, needs a_left): binary32 [p], replicated.  a_right_inv (nullable):
+ * the INVERSE matrix A_r^-1 [q][q] in dtype, applied to every group of q input features; v_right (nullable, needs
+ * a_right_inv): binary32 [q], the shift of T_r, replicated.  p, q: multiples of 32 (bf16) / 16 (fp32), at least 32.
+ * Products on the matrix cores with binary32 accumulation, each rounded to dtype; the bias uses the stored w_out.
+ * workspace: model_fold_workspace bytes; matrices and workspace 16-byte aligned.  AE_EINVAL otherwise.
+ * model_fold_embedding: every row w_j of the table e [vocab][d] becomes A w_j + v (a [d][d] in dtype, v binary32
+ * [d] or null), written to e_out (distinct from e). */
+int model_fold_workspace(int64_t out, int64_t in, int64_t p, int64_t q, int dtype, int64_t* bytes);
+int model_fold_linear(const void* w, const float* b, int64_t out, int64_t in, const void* a_left, int64_t p,
+                      const float* v_left, const void* a_right_inv, int64_t q, const float* v_right, int dtype,
+                      void* w_out, float* b_out, void* workspace, void* stream);
+int model_fold_embedding(const void* e, int64_t vocab, int64_t d, const void* a, const float* v, int dtype, void* e_out,
+                         void* stream);
+
 /* Measurement aid: TFLOP/s of a loop of nothing but independent 32x32x16 bf16 matrix-core
  * instructions on every compute unit (two workgroups of four wavefronts each, two wavefronts per
  * SIMD), the practical ceiling beside the nominal peak; with lds_reads = 6 each wavefront also reads

@@ -23,7 +23,7 @@ SYMBOLS = [
     "model_set_sample_offset", "model_forward", "model_backward", "model_loss_mse", "model_noise",
     "model_pnorm_awgn", "model_gen_bits", "model_count_errors", "model_num_steps", "model_step_info",
     "model_get_activation", "model_timing_enable", "model_set_overlap", "model_calibrate_mfma", "model_mx_quantize", "model_transform_mse_workspace",
-    "model_transform_mse", "model_lu_workspace", "model_lu_compose", "model_lu_backward", "model_vol_penalty", "model_lu_timing", "model_timing_slots",
+    "model_transform_mse", "model_lu_workspace", "model_lu_compose", "model_lu_backward", "model_vol_penalty", "model_lu_timing", "model_fold_workspace", "model_fold_linear", "model_fold_embedding", "model_timing_slots",
     "model_timing_read", "model_timing_reset", "model_last_error",
 ]
 
@@ -68,6 +68,9 @@ def _load():
     L.model_lu_backward.argtypes = [vp, vp, vp, vp, vp, vp, C.c_int64, C.c_int, vp, vp, vp, vp, vp]
     L.model_vol_penalty.argtypes = [vp, C.c_int64, vp, vp, vp]
     L.model_lu_timing.argtypes = [C.c_int, C.POINTER(C.c_double), i64p]
+    L.model_fold_workspace.argtypes = [C.c_int64, C.c_int64, C.c_int64, C.c_int64, C.c_int, i64p]
+    L.model_fold_linear.argtypes = [vp, vp, C.c_int64, C.c_int64, vp, C.c_int64, vp, vp, C.c_int64, vp, C.c_int, vp, vp, vp, vp]
+    L.model_fold_embedding.argtypes = [vp, C.c_int64, C.c_int64, vp, vp, C.c_int, vp, vp]
     L.model_timing_slots.argtypes = [vp, C.POINTER(C.c_int)]
     L.model_timing_read.argtypes = [vp, C.c_int, C.c_char_p, C.c_int, C.POINTER(C.c_double), i64p,
                                     C.POINTER(C.c_double), C.POINTER(C.c_double)]
@@ -279,6 +282,34 @@ def model_lu_timing(enable):
     ms, n = C.c_double(0.0), C.c_int64(0)
     _check(lib.model_lu_timing(1 if enable else 0, C.byref(ms), C.byref(n)))
     return ms.value, n.value
+
+
+def model_fold_workspace(out, in_, p, q, dtype):
+    n = C.c_int64()
+    _check(lib.model_fold_workspace(out, in_, p, q, dtype, C.byref(n)))
+    return n.value
+
+
+def model_fold_linear(w, b, out, in_, a_left, v_left, a_right_inv, v_right, w_out, b_out, workspace):
+    dtype = AE_BF16 if w.dtype == torch.bfloat16 else AE_F32
+    assert w.numel() == out * in_ and w_out.numel() == out * in_ and w_out.dtype == w.dtype and b_out.numel() == out
+    p = 0 if a_left is None else int(round(a_left.numel() ** 0.5))
+    q = 0 if a_right_inv is None else int(round(a_right_inv.numel() ** 0.5))
+    assert (a_left is None or (a_left.numel() == p * p and a_left.dtype == w.dtype)) and (v_left is None or v_left.numel() == p)
+    assert (a_right_inv is None or (a_right_inv.numel() == q * q and a_right_inv.dtype == w.dtype)) and (v_right is None or v_right.numel() == q)
+    assert b is None or b.numel() == out
+    assert workspace.numel() * workspace.element_size() >= model_fold_workspace(out, in_, p, q, dtype)
+    f32 = lambda t: _ptr(None) if t is None else _ptr(t, torch.float32)
+    _check(lib.model_fold_linear(_ptr(w), f32(b), out, in_, _ptr(a_left), p, f32(v_left), _ptr(a_right_inv), q, f32(v_right),
+                                 dtype, _ptr(w_out), _ptr(b_out, torch.float32), _ptr(workspace), _stream()))
+
+
+def model_fold_embedding(e, vocab, d, a, v, e_out):
+    dtype = AE_BF16 if e.dtype == torch.bfloat16 else AE_F32
+    assert e.numel() == vocab * d and e_out.numel() == vocab * d and a.numel() == d * d and a.dtype == e.dtype and e_out.dtype == e.dtype
+    assert v is None or v.numel() == d
+    _check(lib.model_fold_embedding(_ptr(e), vocab, d, _ptr(a), _ptr(None) if v is None else _ptr(v, torch.float32), dtype,
+                                    _ptr(e_out), _stream()))
 
 
 def model_calibrate_mfma(lds_reads, random_data=0, iters=4000):
