@@ -336,6 +336,91 @@ def bench_lu_param(torch, ae, args):
     }
 
 
+# measured HBM bytes per launch of the folding products (profiles/fold_attention.md)
+FOLD_TRAFFIC_BYTES = {"bf16": 1.43e8}     # average of the six product launches of a step
+
+
+def bench_fold(torch, ae, args):
+    """One step = folding T1 (residual stream, d = 4 096) and T2 (one 128 x 128 matrix shared by the heads) into the four
+    projections of one attention block of an 8-billion-parameter-class model: Q [4096][4096] and K [1024][4096]
+    (T1^-1 on the input), V [1024][4096] (T2 after, T1^-1 before), O [4096][4096] (A1 after, T2^-1 before).
+    Algorithmic FLOPs: 2 * out * in * (side of each factor), summed over the factors."""
+    d, dh, dkv = 4096, 128, 1024
+    bf = args.dtype == "bf16"
+    td = torch.bfloat16 if bf else torch.float32
+    rng = np.random.default_rng(21)
+    a1, v1, a1inv, _ = wl.make_transform(d, seed=21, bf16=bf, kind="affine")
+    a2, v2, a2inv, _ = wl.make_transform(dh, seed=22, bf16=bf, kind="affine")
+    dev = lambda a, t=td: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda().to(t).contiguous()
+    f32 = torch.float32
+    layers = []            # (name, out, in, a_left, v_left, a_right_inv, v_right)
+    for name, out, inn, al, vl, ar, vr in (("q", d, d, None, None, a1inv, v1), ("k", dkv, d, None, None, a1inv, v1),
+                                           ("v", dkv, d, a2, v2, a1inv, v1), ("o", d, d, a1, None, a2inv, v2)):
+        W = (rng.standard_normal((out, inn)) / np.sqrt(inn)).astype(np.float32)
+        b = rng.standard_normal(out).astype(np.float32)
+        layers.append(dict(name=name, out=out, inn=inn, W_h=W, b_h=b, al_h=al, vl_h=vl, ar_h=ar, vr_h=vr,
+                           W=dev(W), b=dev(b, f32), al=None if al is None else dev(al), vl=None if vl is None else dev(vl, f32),
+                           ar=None if ar is None else dev(ar), vr=None if vr is None else dev(vr, f32),
+                           w_out=torch.empty((out, inn), dtype=td, device="cuda"), b_out=torch.empty(out, device="cuda")))
+    ws_bytes = max(ae.model_fold_workspace(l["out"], l["inn"], 0 if l["al"] is None else l["al"].shape[0],
+                                           0 if l["ar"] is None else l["ar"].shape[0], ae.DTYPES[args.dtype]) for l in layers)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+
+    def step():
+        for l in layers:
+            ae.model_fold_linear(l["W"], l["b"], l["out"], l["inn"], l["al"], l["vl"], l["ar"], l["vr"], l["w_out"], l["b_out"], ws)
+
+    flops = 0.0
+    for l in layers:
+        if l["ar"] is not None:
+            flops += 2.0 * l["out"] * l["inn"] * l["ar"].shape[0]
+        if l["al"] is not None:
+            flops += 2.0 * l["out"] * l["inn"] * l["al"].shape[0]
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    step_ms = e0.elapsed_time(e1) / args.steps
+    ach = flops / step_ms / 1e9
+    from oracle import fold_oracle as fo
+    c0 = time.perf_counter()
+    reps = 0
+    while time.perf_counter() - c0 < (1.0 if args.no_cpu_baseline else 12.0):
+        for l in layers:
+            fo.fold_linear(l["W_h"], l["b_h"], l["al_h"], l["vl_h"], l["ar_h"], l["vr_h"])
+        reps += 1
+    ct = time.perf_counter() - c0
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = 1
+    return {
+        "metric": "attention blocks/sec, folding T1 and T2 into the Q, K, V, O projections (d = 4096, 8 KV heads of 128)",
+        "value": args.steps / dt, "unit": "blocks/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": args.dtype, "data": "synthetic",
+        "config": {"workload": "fold_attention: W~ = A_l W A_r^-1, b~ = A_l b - W~ v_r + v_l for Q, K, V, O", "d": d, "d_head": dh,
+                   "kv_features": dkv},
+        # all kernels of the step under the events: six products, five transposes, four bias kernels
+        "roofline": {"bound": "mfma", "kernel": "k_igemm (dense)", "achieved": ach, "peak": PEAK[args.dtype], "unit": "TFLOP/s",
+                     "frac": ach / PEAK[args.dtype], "traffic": FOLD_TRAFFIC_BYTES.get(args.dtype), "avg_ms": step_ms / 6,
+                     "launches_per_step": 6, "flops_per_launch": flops / 6, "step_ms_under_events": step_ms},
+        "cpu_baseline": {"value": reps / ct, "unit": "blocks/s", "cores": cores, "kind": "oracle",
+                         "sample": "%d full steps (float64) in %.1f s" % (reps, ct)},
+    }
+
+
 def cpu_baseline(name, budget_s=20.0):
     """The oracle as it stands, on a bounded sample of the same workload (same layer list and
     resolution, smaller batch), timed on this machine's host cores."""
@@ -391,6 +476,9 @@ def main():
     ap.add_argument("--lu-param", action="store_true",
                     help="benchmark the LU parametrisation of Eq. (4) (compose, regulariser, parameter gradients; d = 4096) "
                          "instead of a network: one JSON line with roofline and cpu_baseline")
+    ap.add_argument("--fold", action="store_true",
+                    help="benchmark the folding of two affine transformations into the four projections of one attention block "
+                         "(d = 4096) instead of a network: one JSON line with roofline and cpu_baseline")
     ap.add_argument("--calibrate-mfma", action="store_true",
                     help="only run the library's plain matrix-core loop (with and without LDS fragment reads) and exit")
     ap.add_argument("--channel-sweep", action="store_true",
@@ -421,6 +509,9 @@ def main():
         return
     if args.lu_param:
         print(json.dumps(bench_lu_param(torch, ae, args)))
+        return
+    if args.fold:
+        print(json.dumps(bench_fold(torch, ae, args)))
         return
     if args.calibrate_mfma:
         res = {"kernel": "k_calib_mfma", "nominal_peak_tflops": PEAK["bf16"]}

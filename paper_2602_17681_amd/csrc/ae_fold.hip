@@ -85,11 +85,47 @@ __global__ __launch_bounds__(256) void k_fold_bias(const T* __restrict__ wt, con
   if (a_left) {
     const int64_t g = o / p;
     const int r = (int)(o - g * p);
-    if (b) for (int k = lane; k < p; k += 64) acc += (double)Store<T>::ld(a_left + (int64_t)r * p + k) * (double)b[g * p + k];
+    if (b) {                                               // p is a multiple of 16: eight entries per lane and pass
+      for (int k = lane * 8; k < p; k += 512) {
+        float av[8];
+        if (sizeof(T) == 2) {
+          Store<bf16_t>::ldv(reinterpret_cast<const bf16_t*>(a_left) + (int64_t)r * p + k, av);
+        } else {
+          const float* pa = reinterpret_cast<const float*>(a_left) + (int64_t)r * p + k;
+          const float4 a = *reinterpret_cast<const float4*>(pa), c = *reinterpret_cast<const float4*>(pa + 4);
+          av[0] = a.x; av[1] = a.y; av[2] = a.z; av[3] = a.w; av[4] = c.x; av[5] = c.y; av[6] = c.z; av[7] = c.w;
+        }
+        const float* pb = b + g * p + k;
+        float part = 0.0f;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) part = fmaf(av[t], pb[t], part);
+        acc += (double)part;
+      }
+    }
   } else if (b && lane == 0) {
     acc = (double)b[o];
   }
-  if (v_right) for (int64_t j = lane; j < in; j += 64) acc -= (double)Store<T>::ld(wt + o * in + j) * (double)v_right[j % q];
+  if (v_right) {
+    if ((in & 7) == 0 && (q & 7) == 0) {                   // eight entries (16 or 32 bytes) per lane and pass
+      for (int64_t j = (int64_t)lane * 8; j < in; j += 512) {
+        float wv[8];
+        if (sizeof(T) == 2) {
+          Store<bf16_t>::ldv(reinterpret_cast<const bf16_t*>(wt) + o * in + j, wv);
+        } else {
+          const float* pw = reinterpret_cast<const float*>(wt) + o * in + j;
+          const float4 a = *reinterpret_cast<const float4*>(pw), c = *reinterpret_cast<const float4*>(pw + 4);
+          wv[0] = a.x; wv[1] = a.y; wv[2] = a.z; wv[3] = a.w; wv[4] = c.x; wv[5] = c.y; wv[6] = c.z; wv[7] = c.w;
+        }
+        const float* pv = v_right + j % q;                 // a chunk of eight never straddles a group of q
+        float part = 0.0f;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) part = fmaf(wv[t], pv[t], part);
+        acc -= (double)part;
+      }
+    } else {
+      for (int64_t j = lane; j < in; j += 64) acc -= (double)Store<T>::ld(wt + o * in + j) * (double)v_right[j % q];
+    }
+  }
   acc = wave_sum(acc);
   if (lane == 0) b_out[o] = (float)(acc + (v_left ? (double)v_left[o % p] : 0.0));
 }
