@@ -22,7 +22,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch (fetched + written) of a kernel family, measured with rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE on this workload and scaled by the same counters of a plain 256 MiB copy (fetch x2.000,
 # write x1.000); commands and per-kernel table: profiles/cfg5_hbm_traffic.md.  Unmeasured: None.
-TRAFFIC_BYTES_PER_LAUNCH = {"cfg5": {"k_igemm": 87.1e6, "k_wgrad": 74.8e6}}
+TRAFFIC_BYTES_PER_LAUNCH = {"cfg5": {"k_igemm": 85.5e6, "k_wgrad": 74.8e6}}
 
 
 def build_case(name, torch, ae, batch=None):
