@@ -194,7 +194,7 @@ def bench_mx_quant(torch, ae, args):
 LU_TRAFFIC_BYTES = {"bf16": 2.07e8}
 
 # measured HBM bytes per launch of the two GEMMs of the transformation error (profiles/transform_mse.md)
-TMSE_TRAFFIC_BYTES = {"bf16": 1.396e9}   # average of the two GEMM launches (1.301 GB and 1.491 GB)
+TMSE_TRAFFIC_BYTES = {"bf16": 9.62e8}   # average of the two GEMM launches (0.941 GB and 0.984 GB)
 
 
 def bench_transform_mse(torch, ae, args):
@@ -337,7 +337,7 @@ def bench_lu_param(torch, ae, args):
 
 
 # measured HBM bytes per launch of the folding products (profiles/fold_attention.md)
-FOLD_TRAFFIC_BYTES = {"bf16": 1.43e8}     # average of the six product launches of a step
+FOLD_TRAFFIC_BYTES = {"bf16": 1.29e8}     # average of the six product launches of a step
 
 
 def bench_fold(torch, ae, args):

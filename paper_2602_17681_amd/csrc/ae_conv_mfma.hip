@@ -275,7 +275,7 @@ __device__ __forceinline__ void igemm_epilogue(floatx16 (&acc)[BM / WGM / 32][BN
   }
   if (p.partial) {
     __syncthreads();
-    for (int i = tid; i < 2 * BN; i += 256) {
+    for (int i = tid; i < 2 * BN; i += WGM * WGN * 64) {
       const int q = i / BN, c = i - q * BN;
       float t = 0.0f;
 #pragma unroll
@@ -374,21 +374,22 @@ struct SlabReads<KS, KS, MI, NJ, BKB> {
 // the workgroup barrier makes every wave's loads visible and also guarantees that the stage
 // about to be refilled has been read by everybody.
 template <typename T, int BM, int BN, int WGM, int WGN, int BKB, bool INTERIOR, bool DMA, int EPI = 0>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k_igemm(IgemmParams p) {
+__global__ __launch_bounds__(WGM * WGN * 64) __attribute__((amdgpu_waves_per_eu(2))) void k_igemm(IgemmParams p) {
   static_assert(EPI == 0 || INTERIOR, "the special epilogues exist for check-free tiles only");
-  static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
+  static_assert(WGM * WGN == 4 || WGM * WGN == 8, "four or eight wavefronts per workgroup");
+  constexpr int NT = WGM * WGN * 64;            // threads: all of them load, each wavefront owns a WM x WN part of the tile
   static_assert(BKB == 64 || BKB == 128, "slab row bytes");
   constexpr int ES = (int)sizeof(T);
   constexpr int BK = BKB / ES;                  // K elements per slab
   constexpr int CPR = BKB / 16;                 // 16-byte chunks per slab row
-  constexpr int RSTEP = 256 / CPR;              // rows covered by one pass of the 256 loader threads
+  constexpr int RSTEP = NT / CPR;               // rows covered by one pass of the loader threads
   constexpr int WM = BM / WGM, WN = BN / WGN;   // wave tile
   constexpr int MI = WM / 32, NJ = WN / 32;     // 32x32 MFMA tiles per wave
   constexpr int A_CHUNKS = BM / RSTEP, B_CHUNKS = BN / RSTEP;
   constexpr int SW = WN + 16 / ES;              // staging row stride of the epilogue (elements): +16 bytes
   constexpr int NSTAGE = DMA ? 3 : 2;
   constexpr int SLAB_BYTES = NSTAGE * (BM + BN) * BKB;
-  constexpr int STAGE_BYTES = 4 * 32 * SW * ES;
+  constexpr int STAGE_BYTES = (NT / 64) * 32 * SW * ES;
   __shared__ __attribute__((aligned(16))) char smem[SLAB_BYTES > STAGE_BYTES ? SLAB_BYTES : STAGE_BYTES];
   char* const sA = smem;                        // [NSTAGE][BM*BKB]
   char* const sB = smem + NSTAGE * BM * BKB;    // [NSTAGE][BN*BKB]
@@ -517,16 +518,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   if (ci0 != 0) IGEMM_TAP();                     // a split that starts inside a tap (the loaders compute a tap's offsets at its first slab)
   if constexpr (DMA) {
     constexpr int L = A_CHUNKS + B_CHUNKS;       // loads per thread and slab
-    static_assert(RSTEP * BKB == 4096, "one pass of the loader covers 4 KB");
+    static_assert(RSTEP * BKB == NT * 16, "one pass of the loader covers 16 bytes per thread");
 #define IGEMM_DMA(STG)                                                                                       \
   {                                                                                                          \
     if (ci0 == 0) IGEMM_TAP();                                                                               \
     char* const da = sA + (STG) * BM * BKB + wave * 1024;                                                    \
     char* const db = sB + (STG) * BN * BKB + wave * 1024;                                                    \
     _Pragma("unroll") for (int i = 0; i < A_CHUNKS; ++i)                                                     \
-        dma_load16(rX, da + i * 4096, a_off[i] + (unsigned)ci0 * (unsigned)ES);                              \
+        dma_load16(rX, da + i * (NT * 16), a_off[i] + (unsigned)ci0 * (unsigned)ES);                         \
     _Pragma("unroll") for (int i = 0; i < B_CHUNKS; ++i)                                                     \
-        dma_load16(rW, db + i * 4096, b_off[i] + kbyte);                                                     \
+        dma_load16(rW, db + i * (NT * 16), b_off[i] + kbyte);                                                \
     ci0 += BK;                                                                                               \
     kbyte += BKB;                                                                                            \
     if (ci0 == p.Cin) { ci0 = 0; ++rs; }                                                                     \
@@ -841,7 +842,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
 struct IgemmTile { int bm, bn, bkb; };
 
 // Largest tile that still gives every compute unit about two workgroups.
-IgemmTile pick_tile(int64_t M, int cout, int cin, int es) {
+IgemmTile pick_tile(int64_t M, int cout, int cin, int es, bool wide = true) {
+  // large dense bf16 products whose 256 x 256 tiles all lie inside the output and still fill the chip: eight
+  // wavefronts per workgroup, a third fewer operand bytes through LDS per multiply-add than 256 x 128
+  if (wide && es == 2 && cout % 256 == 0 && M % 256 == 0 && (M / 256) * (cout / 256) >= 256) return IgemmTile{256, 256, 64};
   const int bn = cout > 64 ? 128 : 64;
   const int64_t tiles_n = (cout + bn - 1) / bn;
   int bm = es == 2 ? 256 : 128;                 // 256-row tiles: bf16 only (register budget)
@@ -902,7 +906,7 @@ static int conv_mfma_splits(const ConvArgs& a0) {
   const ConvArgs a = conv_effective(a0);
   const int es = (int)dtype_size(a.dtype);
   const int64_t M = (int64_t)a.n * a.hc * a.wc;
-  const IgemmTile t = pick_tile(M, a.cout, a.cin, es);
+  const IgemmTile t = pick_tile(M, a.cout, a.cin, es, a0.tri == 0);
   const int64_t tiles = ((M + t.bm - 1) / t.bm) * ((a.cout + t.bn - 1) / t.bn);
   const int64_t KT = (int64_t)a.k * a.k * a.cin * es / t.bkb;
   if (tiles >= 256 || KT < 16) return 1;          // one workgroup per compute unit or more: no split
@@ -940,7 +944,7 @@ bool conv_epi_usable(const ConvArgs& a) {
   if (a.epi == CONV_EPI_RESID && (!a.partial || !a.resid)) return false;
   if (a.epi == CONV_EPI_MXQ && a.partial) return false;
   const IgemmTile t = pick_tile(a.n, a.cout, a.cin, (int)dtype_size(a.dtype));
-  return t.bn == 128 && a.n % t.bm == 0;
+  return (t.bn == 128 || t.bn == 256) && a.n % t.bm == 0;
 }
 
 bool conv_up_dgrad_usable(const ConvArgs& a0) {
@@ -997,7 +1001,9 @@ int launch_conv_mfma(const ConvArgs& a0, hipStream_t s) {
 #undef PATCH_LAUNCH_W
     return launch_status("conv3_patch");
   }
-  const IgemmTile t = pick_tile(p.M, a.cout, a.cin, es);
+  // the wide tile exists without run-time checks only; tiles of very different K lengths balance better when smaller
+  const bool wide_ok = a0.tri == 0 && !a.y_aux && a.act != ACT_SIGMOID && !(a.partial && a.act != ACT_NONE) && a0.geom == CONV_PLAIN;
+  const IgemmTile t = pick_tile(p.M, a.cout, a.cin, es, wide_ok);
   p.tiles_n = (a.cout + t.bn - 1) / t.bn;
   const int64_t tiles_m = (p.M + t.bm - 1) / t.bm;
   const int KT = (int)((int64_t)p.K * es / t.bkb);
@@ -1029,7 +1035,10 @@ int launch_conv_mfma(const ConvArgs& a0, hipStream_t s) {
   if (a0.epi != CONV_EPI_NONE) {
     // (conv_epi_usable: interior tiles, BN = 128, no split)
 #define IGEMM_LAUNCH_EPI(T, BMV, E) hipLaunchKernelGGL((k_igemm<T, BMV, 128, 2, 2, 64, true, true, E>), grid, dim3(256), 0, s, p)
-    if (a.dtype == AE_BF16) {
+    if (t.bn == 256) {
+      if (a0.epi == CONV_EPI_MXQ) hipLaunchKernelGGL((k_igemm<bf16_t, 256, 256, 2, 4, 64, true, true, 1>), grid, dim3(512), 0, s, p);
+      else hipLaunchKernelGGL((k_igemm<bf16_t, 256, 256, 2, 4, 64, true, true, 2>), grid, dim3(512), 0, s, p);
+    } else if (a.dtype == AE_BF16) {
       if (t.bm == 256) { if (a0.epi == CONV_EPI_MXQ) IGEMM_LAUNCH_EPI(bf16_t, 256, 1); else IGEMM_LAUNCH_EPI(bf16_t, 256, 2); }
       else { if (a0.epi == CONV_EPI_MXQ) IGEMM_LAUNCH_EPI(bf16_t, 128, 1); else IGEMM_LAUNCH_EPI(bf16_t, 128, 2); }
     } else {
@@ -1038,7 +1047,8 @@ int launch_conv_mfma(const ConvArgs& a0, hipStream_t s) {
 #undef IGEMM_LAUNCH_EPI
     return launch_status("conv_mfma_epi");
   }
-  if (t.bm == 256 && t.bn == 128) IGEMM_LAUNCH_K(bf16_t, 256, 128, 2, 2, 64);
+  if (t.bn == 256) hipLaunchKernelGGL((k_igemm<bf16_t, 256, 256, 2, 4, 64, true, true>), grid, dim3(512), 0, s, p);   // (pick_tile: interior only)
+  else if (t.bm == 256 && t.bn == 128) IGEMM_LAUNCH_K(bf16_t, 256, 128, 2, 2, 64);
   else if (t.bm == 256) IGEMM_LAUNCH_K(bf16_t, 256, 64, 4, 1, 64);
   else if (t.bn == 128) IGEMM_LAUNCH(128, 128, 2, 2);
   else IGEMM_LAUNCH(128, 64, 2, 2);
