@@ -67,3 +67,22 @@ def test_bad_arguments(ae):
     assert ae.lib.model_loss_mse(None, None, 4, 0, None, None, None) == -1
     assert ae.lib.model_noise(0, 0, 1, 1, None, None) == -1
     ae.lib.model_destroy(None)   # no-op
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU: bench.py --gpus N with N > 1 exits with a message (before touching any GPU)."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in (r.stderr + r.stdout)
+
+
+def test_host_only_argument_checks_of_the_widening_entry_points(ae):
+    """Size and argument errors are reported on the host, before any GPU call."""
+    n = C.c_int64()
+    assert ae.lib.model_lu_workspace(48, 0, C.byref(n)) == -1 and "multiple of 32" in ae.model_last_error()
+    assert ae.lib.model_lu_workspace(4096, 1, C.byref(n)) == 0 and n.value == 6 * 4096 * 4096 * 2 + 16384
+    assert ae.lib.model_fold_workspace(4096, 4096, 4096, 128, 1, C.byref(n)) == 0 and n.value == (128 * 128 + 3 * 4096 * 4096) * 2 + 1024
+    assert ae.lib.model_transform_mse_workspace(16384, 4096, 1, C.byref(n)) == 0 and n.value == 64 * 2 * 4096 * 4
+    assert ae.lib.model_mx_quantize(None, None, 4, 64, 32, 1, None) == -1
+    assert ae.lib.model_vol_penalty(None, 8, None, None, None) == -1
