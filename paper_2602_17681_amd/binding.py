@@ -23,7 +23,7 @@ SYMBOLS = [
     "model_set_sample_offset", "model_forward", "model_backward", "model_loss_mse", "model_noise",
     "model_pnorm_awgn", "model_gen_bits", "model_count_errors", "model_num_steps", "model_step_info",
     "model_get_activation", "model_timing_enable", "model_set_overlap", "model_calibrate_mfma", "model_mx_quantize", "model_transform_mse_workspace",
-    "model_transform_mse", "model_lu_workspace", "model_lu_compose", "model_lu_backward", "model_vol_penalty", "model_lu_timing", "model_fold_workspace", "model_fold_linear", "model_fold_embedding", "model_timing_slots",
+    "model_transform_mse", "model_lu_workspace", "model_lu_compose", "model_lu_backward", "model_vol_penalty", "model_lu_inverse_workspace", "model_lu_inverse", "model_lu_timing", "model_fold_workspace", "model_fold_linear", "model_fold_embedding", "model_timing_slots",
     "model_timing_read", "model_timing_reset", "model_last_error",
 ]
 
@@ -68,6 +68,8 @@ def _load():
     L.model_lu_backward.argtypes = [vp, vp, vp, vp, vp, vp, C.c_int64, C.c_int, vp, vp, vp, vp, vp]
     L.model_vol_penalty.argtypes = [vp, C.c_int64, vp, vp, vp]
     L.model_lu_timing.argtypes = [C.c_int, C.POINTER(C.c_double), i64p]
+    L.model_lu_inverse_workspace.argtypes = [C.c_int64, i64p]
+    L.model_lu_inverse.argtypes = [vp, vp, vp, vp, vp, C.c_int64, C.c_int, vp, vp, vp]
     L.model_fold_workspace.argtypes = [C.c_int64, C.c_int64, C.c_int64, C.c_int64, C.c_int, i64p]
     L.model_fold_linear.argtypes = [vp, vp, C.c_int64, C.c_int64, vp, C.c_int64, vp, vp, C.c_int64, vp, C.c_int, vp, vp, vp, vp]
     L.model_fold_embedding.argtypes = [vp, C.c_int64, C.c_int64, vp, vp, C.c_int, vp, vp]
@@ -269,6 +271,18 @@ def model_lu_backward(g, lp, up, log_s, sign_s, perm, d, d_lp, d_up, d_log_s, wo
     assert workspace.numel() * workspace.element_size() >= model_lu_workspace(d, dtype)
     _check(lib.model_lu_backward(_ptr(g), *_lu_params(lp, up, log_s, sign_s, perm, d), d, dtype, _ptr(d_lp, torch.float32),
                                  _ptr(d_up, torch.float32), _ptr(d_log_s, torch.float32), _ptr(workspace), _stream()))
+
+
+def model_lu_inverse_workspace(d):
+    n = C.c_int64()
+    _check(lib.model_lu_inverse_workspace(d, C.byref(n)))
+    return n.value
+
+
+def model_lu_inverse(lp, up, log_s, sign_s, perm, d, a_inv_out, workspace):
+    dtype = AE_BF16 if a_inv_out.dtype == torch.bfloat16 else AE_F32
+    assert a_inv_out.numel() == d * d and workspace.numel() * workspace.element_size() >= model_lu_inverse_workspace(d)
+    _check(lib.model_lu_inverse(*_lu_params(lp, up, log_s, sign_s, perm, d), d, dtype, _ptr(a_inv_out), _ptr(workspace), _stream()))
 
 
 def model_vol_penalty(log_s, d, value, d_log_s=None):

@@ -217,6 +217,98 @@ void launch_build(const LuSrc& q, void* out, hipStream_t s) {
   hipLaunchKernelGGL((k_lu_build<T, SRC, TR>), dim3(q.d / 32, q.d / 32), dim3(256), 0, s, q, reinterpret_cast<T*>(out));
 }
 
+// ---- inverse of the parametrised matrix ---------------------------------------------------------------------
+// A^-1 = (U + diag s)^-1 L^-1 P^T.  Both triangular inverses use the same blocked recursion on a LOWER triangular
+// matrix M (L itself; (U + diag s)^T for the upper factor): 128 x 128 diagonal blocks are inverted by substitution,
+// then neighbouring inverses X11, X22 of blocks of size b merge into the inverse of the 2b x 2b block,
+//     [[X11, 0], [-X22 M21 X11, X22]],
+// with the two products on the matrix cores in binary32.  Every level keeps its block inverses and their
+// transposes as contiguous [blocks][b][b] arrays, so the products are plain dense ones.
+
+// entry (r, c), c <= r, of the lower triangular matrix: WHICH 0: L; 1: (U + diag s)^T
+template <int WHICH>
+__device__ __forceinline__ float tri_elem(const LuSrc& q, int r, int c) {
+  if (c > r) return 0.0f;
+  if (WHICH == 0) return c < r ? q.lp[(int64_t)r * q.d + c] : 1.0f;
+  return c < r ? q.up[(int64_t)c * q.d + r] : q.sign[c] * expf(q.log_s[c]);
+}
+
+// X = M_bb^-1 for every 128 x 128 diagonal block b (one workgroup each): thread j solves column j by forward
+// substitution; x[b][128][128] and its transpose xt are written.
+template <int WHICH>
+__global__ __launch_bounds__(128) void k_tri_diag_inverse(LuSrc q, float* __restrict__ x, float* __restrict__ xt) {
+  __shared__ float mb[128][129];
+  __shared__ float xb[128][129];
+  const int b = blockIdx.x, j = threadIdx.x, o = b * 128;
+  for (int i = 0; i < 128; ++i) mb[i][j] = tri_elem<WHICH>(q, o + i, o + j);
+  __syncthreads();
+  for (int i = 0; i < 128; ++i) {
+    float v = 0.0f;
+    if (i == j) {
+      v = 1.0f / mb[j][j];
+    } else if (i > j) {
+      float acc = 0.0f;
+      for (int k = j; k < i; ++k) acc = fmaf(mb[i][k], xb[k][j], acc);   // column j of xb is this thread's own
+      v = -acc / mb[i][i];
+    }
+    xb[i][j] = v;
+  }
+  __syncthreads();
+  float* xo = x + (int64_t)b * 128 * 128;
+  float* xto = xt + (int64_t)b * 128 * 128;
+  for (int i = 0; i < 128; ++i) {
+    xo[i * 128 + j] = xb[i][j];
+    xto[i * 128 + j] = xb[j][i];
+  }
+}
+
+// out[p][m][k] = M[(2p+1) b + m][2p b + k]: the sub-diagonal block of every pair, contiguous
+template <int WHICH>
+__global__ __launch_bounds__(256) void k_tri_pack(LuSrc q, int b, int pairs, float* __restrict__ out) {
+  const int64_t n = (int64_t)pairs * b * b;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const int p = (int)(i / ((int64_t)b * b));
+    const int rem = (int)(i - (int64_t)p * b * b);
+    const int m = rem / b, k = rem - m * b;
+    out[i] = tri_elem<WHICH>(q, (2 * p + 1) * b + m, 2 * p * b + k);
+  }
+}
+
+// xn[p] = [[x[2p], 0], [-x21[p], x[2p+1]]] (2b x 2b) and xtn[p] its transpose; 32 x 32 tiles, b % 32 == 0
+__global__ __launch_bounds__(256) void k_tri_assemble(const float* __restrict__ x, const float* __restrict__ x21, int b,
+                                                      float* __restrict__ xn, float* __restrict__ xtn) {
+  __shared__ float tile[32][33];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  const int p = blockIdx.z, r0 = blockIdx.y * 32, c0 = blockIdx.x * 32, n2 = 2 * b;
+  const int64_t bb = (int64_t)b * b;
+  float* xo = xn + (int64_t)p * n2 * n2;
+  float* xto = xtn + (int64_t)p * n2 * n2;
+#pragma unroll
+  for (int jj = 0; jj < 4; ++jj) {
+    const int r = r0 + ty + 8 * jj, c = c0 + tx;
+    float v;
+    if (r < b) v = c < b ? x[(2 * p) * bb + (int64_t)r * b + c] : 0.0f;
+    else v = c < b ? -x21[p * bb + (int64_t)(r - b) * b + c] : x[(2 * p + 1) * bb + (int64_t)(r - b) * b + (c - b)];
+    xo[(int64_t)r * n2 + c] = v;
+    tile[ty + 8 * jj][tx] = v;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int jj = 0; jj < 4; ++jj) xto[(int64_t)(c0 + ty + 8 * jj) * n2 + r0 + tx] = tile[tx][ty + 8 * jj];
+}
+
+// out[r][c] = z[r][perm[c]] in the storage type (z P^T)
+template <typename T>
+__global__ __launch_bounds__(256) void k_lu_inverse_out(const float* __restrict__ z, const int* __restrict__ perm, int d, T* __restrict__ out) {
+  const int64_t n = (int64_t)d * d;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const int r = (int)(i / d), c = (int)(i - (int64_t)r * d);
+    int src = perm[c];
+    if ((unsigned)src >= (unsigned)d) src = c;                         // not a permutation: stay inside the arrays
+    Store<T>::st(out + i, z[(int64_t)r * d + src]);
+  }
+}
+
 template <typename T, int SRC>
 void launch_build_transposed(const LuSrc& q, void* out, hipStream_t s) {
   if (q.d % 64 == 0) hipLaunchKernelGGL((k_lu_build_transposed<T, SRC>), dim3(q.d / 64, q.d / 64), dim3(256), 0, s, q, reinterpret_cast<T*>(out));
@@ -258,6 +350,33 @@ int64_t lu_mat_bytes(int64_t d, int dtype) { return d * d * (int64_t)dtype_size(
 unsigned lu_grid(int64_t items) {
   const int64_t g = (items + 256 * 8 - 1) / (256 * 8);
   return (unsigned)(g < 4096 ? (g < 1 ? 1 : g) : 4096);
+}
+
+// the blocked recursion above for one lower triangular matrix; on return *res / *res_t point at its inverse and the
+// inverse's transpose (each [d][d] binary32, inside buf[0..3])
+template <int WHICH>
+int tri_inverse(const LuSrc& q, float* const (&buf)[4], float* m21, float* tt, float* x21, float** res, float** res_t, hipStream_t s) {
+  const int d = q.d;
+  float *x = buf[0], *xt = buf[1], *xn = buf[2], *xtn = buf[3];
+  hipLaunchKernelGGL((k_tri_diag_inverse<WHICH>), dim3(d / 128), dim3(128), 0, s, q, x, xt);
+  AE_TRY(launch_status("tri_diag_inverse"));
+  for (int b = 128; b < d; b *= 2) {
+    const int pairs = d / (2 * b);
+    const int64_t bb = (int64_t)b * b;
+    hipLaunchKernelGGL((k_tri_pack<WHICH>), dim3(lu_grid(pairs * bb)), dim3(256), 0, s, q, b, pairs, m21);
+    AE_TRY(launch_status("tri_pack"));
+    for (int p = 0; p < pairs; ++p) {
+      AE_TRY(dense_product(xt + (2 * p) * bb, m21 + p * bb, tt + p * bb, b, AE_F32, CONV_TRI_NONE, s));        // (M21 X11)^T
+      AE_TRY(dense_product(x + (2 * p + 1) * bb, tt + p * bb, x21 + p * bb, b, AE_F32, CONV_TRI_NONE, s));     // X22 M21 X11
+    }
+    hipLaunchKernelGGL(k_tri_assemble, dim3(2 * b / 32, 2 * b / 32, pairs), dim3(256), 0, s, (const float*)x, (const float*)x21, b, xn, xtn);
+    AE_TRY(launch_status("tri_assemble"));
+    float* t = x; x = xn; xn = t;
+    t = xt; xt = xtn; xtn = t;
+  }
+  *res = x;
+  *res_t = xt;
+  return AE_OK;
 }
 
 int check_lu_size(const char* who, int64_t d, int dtype) {
@@ -344,6 +463,43 @@ extern "C" int model_lu_backward(const void* g, const float* lp, const float* up
     hipLaunchKernelGGL((k_lu_grad_lower<float>), dim3(grid), dim3(256), 0, s, (const float*)dl, (int)d, d_lp);
   }
   return launch_status("lu_backward");
+}
+
+extern "C" int model_lu_inverse_workspace(int64_t d, int64_t* bytes) {
+  using namespace ae;
+  if (!bytes) return fail(AE_EINVAL, "model_lu_inverse_workspace: null argument");
+  if (d < 128 || d > 16384 || d % 128 != 0 || ((d / 128) & (d / 128 - 1)) != 0)
+    return fail(AE_EINVAL, "model_lu_inverse_workspace: d must be 128 times a power of two, at most 16384");
+  *bytes = (6 * d * d + 3 * (d * d / 4)) * 4 + 1024;
+  return AE_OK;
+}
+
+extern "C" int model_lu_inverse(const float* lp, const float* up, const float* log_s, const float* sign_s, const int* perm,
+                                int64_t d, int dtype, void* a_inv_out, void* workspace, void* stream) {
+  using namespace ae;
+  if (!lp || !up || !log_s || !sign_s || !perm || !a_inv_out || !workspace) return fail(AE_EINVAL, "model_lu_inverse: null argument");
+  if (dtype != AE_F32 && dtype != AE_BF16) return fail(AE_EINVAL, "model_lu_inverse: bad dtype");
+  if (d < 128 || d > 16384 || d % 128 != 0 || ((d / 128) & (d / 128 - 1)) != 0)
+    return fail(AE_EINVAL, "model_lu_inverse: d must be 128 times a power of two, at most 16384");
+  if ((reinterpret_cast<uintptr_t>(workspace) & 15) != 0) return fail(AE_EINVAL, "model_lu_inverse: the workspace must be 16-byte aligned");
+  hipStream_t s = (hipStream_t)stream;
+  const int64_t dd = d * d;
+  float* f = reinterpret_cast<float*>(workspace);
+  float* const buf[4] = {f, f + dd, f + 2 * dd, f + 3 * dd};
+  float* linv_t = f + 4 * dd;                      // (L^-1)^T, kept while the upper factor is inverted
+  float* z = f + 5 * dd;                           // (U + diag s)^-1 L^-1
+  float* m21 = f + 6 * dd;                         // per level: sub-diagonal blocks, (M21 X11)^T, X22 M21 X11
+  float* tt = m21 + dd / 4;
+  float* x21 = tt + dd / 4;
+  LuSrc q{lp, up, log_s, sign_s, nullptr, nullptr, (int)d};
+  float *res = nullptr, *res_t = nullptr;
+  AE_TRY(tri_inverse<0>(q, buf, m21, tt, x21, &res, &res_t, s));
+  AE_HIP(hipMemcpyAsync(linv_t, res_t, dd * 4, hipMemcpyDeviceToDevice, s));
+  AE_TRY(tri_inverse<1>(q, buf, m21, tt, x21, &res, &res_t, s));     // res = ((U + diag s)^T)^-1, res_t = (U + diag s)^-1
+  AE_TRY(dense_product(res_t, linv_t, z, (int)d, AE_F32, CONV_TRI_NONE, s));
+  if (dtype == AE_BF16) hipLaunchKernelGGL((k_lu_inverse_out<bf16_t>), dim3(lu_grid(dd)), dim3(256), 0, s, (const float*)z, perm, (int)d, (bf16_t*)a_inv_out);
+  else hipLaunchKernelGGL((k_lu_inverse_out<float>), dim3(lu_grid(dd)), dim3(256), 0, s, (const float*)z, perm, (int)d, (float*)a_inv_out);
+  return launch_status("lu_inverse_out");
 }
 
 extern "C" int model_lu_timing(int enable, double* gemm_ms, int64_t* launches) {

@@ -146,3 +146,67 @@ def test_full_size_compose_and_backward(ae):
     dlp, dup, dls = _backward(ae, g, params, d, "bf16")
     r_lp, r_up, r_ls = ao.lu_gradients(g, *params)
     assert _close(dlp, r_lp, TOL["bf16"]) and _close(dup, r_up, TOL["bf16"]) and _close(dls, r_ls, TOL["bf16"])
+
+
+# ------------------------------------------------------------------ the inverse of the parametrised matrix
+def _inverse(ae, params, d, dtype):
+    import torch
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    out = torch.full((d, d), float("nan"), dtype=td, device="cuda")
+    ws = torch.empty(ae.model_lu_inverse_workspace(d), dtype=torch.uint8, device="cuda")
+    ae.model_lu_inverse(*_dev(ae, params), d, out, ws)
+    torch.cuda.synchronize()
+    return out.float().cpu().numpy().astype(np.float64)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("d,kind", [(128, "random"), (256, "random"), (512, "bd_hadamard"), (1024, "random"), (2048, "bd_hadamard")])
+def test_inverse_matches_the_inverse_of_the_composed_matrix(ae, d, kind, dtype):
+    """A^-1 from the triangular factors against numpy's inverse of the oracle's A (float64).  The blocked recursion
+    runs in binary32: its error is a few 1e-7 times the condition number of the factors (below 1e2 here), so the
+    binary32 result is held to 1e-4 and the bf16 result to the rounding of the output."""
+    params = wl.make_lu_params(d, seed=d + 7, kind=kind, noise=1e-3 if kind == "bd_hadamard" else 0.0)
+    a = ao.lu_compose(*params)
+    ref = np.linalg.inv(a)
+    got = _inverse(ae, params, d, dtype)
+    assert _close(got, ref, TOL[dtype]), (np.abs(got - ref).max(), np.linalg.cond(a))
+    if dtype == "f32":
+        assert np.abs(a @ got - np.eye(d)).max() < 1e-4
+
+
+def test_inverse_feeds_the_transformation_error(ae):
+    """The whole chain on the GPU: parameters -> A and A^-1 -> E(T), against the oracle chain with numpy's inverse."""
+    import torch
+    from oracle import mx_oracle as mxo
+    d, rows = 512, 512
+    params = wl.make_lu_params(d, seed=21, kind="bd_hadamard", noise=2e-3)
+    dp = _dev(ae, params)
+    a = torch.empty((d, d), dtype=torch.bfloat16, device="cuda")
+    ainv = torch.empty((d, d), dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(max(ae.model_lu_workspace(d, ae.DTYPES["bf16"]), ae.model_lu_inverse_workspace(d)), dtype=torch.uint8, device="cuda")
+    ae.model_lu_compose(*dp, d, a, ws)
+    ae.model_lu_inverse(*dp, d, ainv, ws)
+    x = wl.make_activations(rows, d, seed=5, bf16=True)
+    xt = torch.from_numpy(x).cuda().to(torch.bfloat16)
+    zeros = torch.zeros(d, device="cuda")
+    yq = torch.empty_like(xt)
+    w2 = torch.empty(ae.model_transform_mse_workspace(rows, d, ae.DTYPES["bf16"]) // 4, dtype=torch.float32, device="cuda")
+    eb, et = torch.empty(d // 32, device="cuda"), torch.empty(1, device="cuda")
+    ae.model_transform_mse(xt, a, zeros, ainv, zeros, rows, d, 32, yq, w2, eb, et)
+    a_ref = wl.round_to_bf16(ao.lu_compose(*params).astype(np.float32))
+    ainv_ref = wl.round_to_bf16(np.linalg.inv(ao.lu_compose(*params)).astype(np.float32))
+    e_o, _, _ = mxo.transform_mse(x, a_ref, np.zeros(d, np.float32), ainv_ref, 32, storage="bf16")
+    assert abs(et.item() - e_o) <= 2e-2 * e_o, (et.item(), e_o)
+
+
+def test_inverse_argument_checks(ae):
+    import torch
+    t = torch.zeros(128 * 128, device="cuda")
+    p = C.c_void_p(t.data_ptr())
+    n = C.c_int64()
+    assert ae.lib.model_lu_inverse_workspace(384, C.byref(n)) == -1        # 3 blocks: not a power of two
+    assert ae.lib.model_lu_inverse_workspace(64, C.byref(n)) == -1
+    assert ae.lib.model_lu_inverse_workspace(256, C.byref(n)) == 0 and n.value == (6 * 256 * 256 + 3 * 256 * 256 // 4) * 4 + 1024
+    assert ae.lib.model_lu_inverse(p, p, p, p, p, 384, 0, p, p, None) == -1
+    assert ae.lib.model_lu_inverse(p, p, p, p, p, 128, 3, p, p, None) == -1
+    assert ae.lib.model_lu_inverse(None, p, p, p, p, 128, 0, p, p, None) == -1
