@@ -303,6 +303,19 @@ def bench_lu_param(torch, ae, args):
     torch.cuda.synchronize()
     gemm_ms, launches = ae.model_lu_timing(False)
     avg_ms = gemm_ms / max(launches, 1)
+    # beside the step: the inverse of the same matrix (what the transformation error and the folding take with A)
+    inv_ms = None
+    if d % 128 == 0 and (d // 128) & (d // 128 - 1) == 0:
+        ainv = torch.empty((d, d), dtype=td, device="cuda")
+        wsi = torch.empty(ae.model_lu_inverse_workspace(d), dtype=torch.uint8, device="cuda")
+        for _ in range(3):
+            ae.model_lu_inverse(lp, up, ls, sg, perm, d, ainv, wsi)
+        e0.record()
+        for _ in range(10):
+            ae.model_lu_inverse(lp, up, ls, sg, perm, d, ainv, wsi)
+        e1.record()
+        torch.cuda.synchronize()
+        inv_ms = e0.elapsed_time(e1) / 10
     flops = 2.0 * d ** 3                     # 3 x (2/3) d^3
     ach = flops / 3.0 / avg_ms / 1e9
     es = a.element_size()
@@ -325,7 +338,8 @@ def bench_lu_param(torch, ae, args):
         "value": args.steps / dt, "unit": "matrices/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": args.dtype, "data": "synthetic",
-        "config": {"workload": "lu_param: A = P L (U + diag s), d = 4096, block-Hadamard initialisation + noise", "d": d},
+        "config": {"workload": "lu_param: A = P L (U + diag s), d = 4096, block-Hadamard initialisation + noise", "d": d,
+                   "inverse_ms_beside_the_step": inv_ms},
         # the three GEMM launches of a step (62 % of its kernel time; twelve element-wise kernels are the rest)
         "roofline": {"bound": "mfma", "kernel": "k_igemm (triangular K ranges)", "achieved": ach, "peak": PEAK[args.dtype],
                      "unit": "TFLOP/s", "frac": ach / PEAK[args.dtype], "achieved_whole_step": flops / step_ms / 1e9,

@@ -231,9 +231,9 @@ int model_lu_backward(const void* g, const float* lp, const float* up, const flo
 int model_vol_penalty(const float* log_s, int64_t d, float* value, float* d_log_s, void* stream);
 /* The inverse of the parametrised matrix, A^-1 = (U + diag s)^-1 L^-1 P^T (what the transformation error and the
  * folding take beside A): a_inv_out [d][d] in dtype.  Both triangular factors are inverted by a blocked recursion
- * (128 x 128 diagonal blocks by substitution, then pairs of blocks merged with two products each), all in
+ * (128 x 128 diagonal blocks by substitution, then neighbouring blocks merged, three launches per level), all in
  * binary32 on the matrix cores; s must not contain zeros.  d: 128 times a power of two, at most 16384.
- * workspace: model_lu_inverse_workspace bytes (6.75 d^2 binary32 values), 16-byte aligned. */
+ * workspace: model_lu_inverse_workspace bytes (six d x d binary32 matrices), 16-byte aligned. */
 int model_lu_inverse_workspace(int64_t d, int64_t* bytes);
 int model_lu_inverse(const float* lp, const float* up, const float* log_s, const float* sign_s, const int* perm, int64_t d,
                      int dtype, void* a_inv_out, void* workspace, void* stream);

@@ -221,11 +221,13 @@ void launch_build(const LuSrc& q, void* out, hipStream_t s) {
 // A^-1 = (U + diag s)^-1 L^-1 P^T.  Both triangular inverses use the same blocked recursion on a LOWER triangular
 // matrix M (L itself; (U + diag s)^T for the upper factor): 128 x 128 diagonal blocks are inverted by substitution,
 // then neighbouring inverses X11, X22 of blocks of size b merge into the inverse of the 2b x 2b block,
-//     [[X11, 0], [-X22 M21 X11, X22]],
-// with the two products on the matrix cores in binary32.  Every level keeps its block inverses and their
-// transposes as contiguous [blocks][b][b] arrays, so the products are plain dense ones.
+//     [[X11, 0], [-X22 M21 X11, X22]].
+// X and X^T live as full d x d binary32 matrices that start block diagonal and fill level by level; one level is
+// three launches of the matrix-core kernel over ALL pairs at once (K-range modes CONV_TRI_PAIR_*):
+//     T' = -(M21 X11)^T  into the upper blocks of a scratch matrix,   X21 = X22 T'^T  in place into X,
+//     X21^T = T' X22^T  in place into X^T.
 
-// entry (r, c), c <= r, of the lower triangular matrix: WHICH 0: L; 1: (U + diag s)^T
+// entry (r, c) of the lower triangular matrix: WHICH 0: L; 1: (U + diag s)^T
 template <int WHICH>
 __device__ __forceinline__ float tri_elem(const LuSrc& q, int r, int c) {
   if (c > r) return 0.0f;
@@ -233,8 +235,24 @@ __device__ __forceinline__ float tri_elem(const LuSrc& q, int r, int c) {
   return c < r ? q.up[(int64_t)c * q.d + r] : q.sign[c] * expf(q.log_s[c]);
 }
 
-// X = M_bb^-1 for every 128 x 128 diagonal block b (one workgroup each): thread j solves column j by forward
-// substitution; x[b][128][128] and its transpose xt are written.
+// mneg = -M (full d x d), x = xt = 0: 32 x 32 tiles
+template <int WHICH>
+__global__ __launch_bounds__(256) void k_tri_prepare(LuSrc q, float* __restrict__ mneg, float* __restrict__ x, float* __restrict__ xt) {
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int r = r0 + ty + 8 * j, c = c0 + tx;
+    const int64_t i = (int64_t)r * q.d + c;
+    // (U + diag s)^T is read along its columns: the tile is small enough for the cache to absorb the stride
+    mneg[i] = -tri_elem<WHICH>(q, r, c);
+    x[i] = 0.0f;
+    xt[i] = 0.0f;
+  }
+}
+
+// X_bb = M_bb^-1 for every 128 x 128 diagonal block b (one workgroup each): thread j solves column j by forward
+// substitution; the block and its transpose are written into the full matrices x and xt.
 template <int WHICH>
 __global__ __launch_bounds__(128) void k_tri_diag_inverse(LuSrc q, float* __restrict__ x, float* __restrict__ xt) {
   __shared__ float mb[128][129];
@@ -247,54 +265,25 @@ __global__ __launch_bounds__(128) void k_tri_diag_inverse(LuSrc q, float* __rest
     if (i == j) {
       v = 1.0f / mb[j][j];
     } else if (i > j) {
-      float acc = 0.0f;
-      for (int k = j; k < i; ++k) acc = fmaf(mb[i][k], xb[k][j], acc);   // column j of xb is this thread's own
-      v = -acc / mb[i][i];
+      // column j of xb is this thread's own; four independent partial sums keep the LDS reads in flight
+      float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
+      int k = j;
+      for (; k + 4 <= i; k += 4) {
+        a0 = fmaf(mb[i][k], xb[k][j], a0);
+        a1 = fmaf(mb[i][k + 1], xb[k + 1][j], a1);
+        a2 = fmaf(mb[i][k + 2], xb[k + 2][j], a2);
+        a3 = fmaf(mb[i][k + 3], xb[k + 3][j], a3);
+      }
+      for (; k < i; ++k) a0 = fmaf(mb[i][k], xb[k][j], a0);
+      v = -((a0 + a1) + (a2 + a3)) / mb[i][i];
     }
     xb[i][j] = v;
   }
   __syncthreads();
-  float* xo = x + (int64_t)b * 128 * 128;
-  float* xto = xt + (int64_t)b * 128 * 128;
   for (int i = 0; i < 128; ++i) {
-    xo[i * 128 + j] = xb[i][j];
-    xto[i * 128 + j] = xb[j][i];
+    x[(int64_t)(o + i) * q.d + o + j] = xb[i][j];
+    xt[(int64_t)(o + i) * q.d + o + j] = xb[j][i];
   }
-}
-
-// out[p][m][k] = M[(2p+1) b + m][2p b + k]: the sub-diagonal block of every pair, contiguous
-template <int WHICH>
-__global__ __launch_bounds__(256) void k_tri_pack(LuSrc q, int b, int pairs, float* __restrict__ out) {
-  const int64_t n = (int64_t)pairs * b * b;
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
-    const int p = (int)(i / ((int64_t)b * b));
-    const int rem = (int)(i - (int64_t)p * b * b);
-    const int m = rem / b, k = rem - m * b;
-    out[i] = tri_elem<WHICH>(q, (2 * p + 1) * b + m, 2 * p * b + k);
-  }
-}
-
-// xn[p] = [[x[2p], 0], [-x21[p], x[2p+1]]] (2b x 2b) and xtn[p] its transpose; 32 x 32 tiles, b % 32 == 0
-__global__ __launch_bounds__(256) void k_tri_assemble(const float* __restrict__ x, const float* __restrict__ x21, int b,
-                                                      float* __restrict__ xn, float* __restrict__ xtn) {
-  __shared__ float tile[32][33];
-  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
-  const int p = blockIdx.z, r0 = blockIdx.y * 32, c0 = blockIdx.x * 32, n2 = 2 * b;
-  const int64_t bb = (int64_t)b * b;
-  float* xo = xn + (int64_t)p * n2 * n2;
-  float* xto = xtn + (int64_t)p * n2 * n2;
-#pragma unroll
-  for (int jj = 0; jj < 4; ++jj) {
-    const int r = r0 + ty + 8 * jj, c = c0 + tx;
-    float v;
-    if (r < b) v = c < b ? x[(2 * p) * bb + (int64_t)r * b + c] : 0.0f;
-    else v = c < b ? -x21[p * bb + (int64_t)(r - b) * b + c] : x[(2 * p + 1) * bb + (int64_t)(r - b) * b + (c - b)];
-    xo[(int64_t)r * n2 + c] = v;
-    tile[ty + 8 * jj][tx] = v;
-  }
-  __syncthreads();
-#pragma unroll
-  for (int jj = 0; jj < 4; ++jj) xto[(int64_t)(c0 + ty + 8 * jj) * n2 + r0 + tx] = tile[tx][ty + 8 * jj];
 }
 
 // out[r][c] = z[r][perm[c]] in the storage type (z P^T)
@@ -352,30 +341,26 @@ unsigned lu_grid(int64_t items) {
   return (unsigned)(g < 4096 ? (g < 1 ? 1 : g) : 4096);
 }
 
-// the blocked recursion above for one lower triangular matrix; on return *res / *res_t point at its inverse and the
-// inverse's transpose (each [d][d] binary32, inside buf[0..3])
+// the blocked recursion above for one lower triangular matrix: x = M^-1 and xt = its transpose ([d][d] binary32 each);
+// mneg and tt are scratch of the same size
 template <int WHICH>
-int tri_inverse(const LuSrc& q, float* const (&buf)[4], float* m21, float* tt, float* x21, float** res, float** res_t, hipStream_t s) {
+int tri_inverse(const LuSrc& q, float* mneg, float* tt, float* x, float* xt, hipStream_t s) {
   const int d = q.d;
-  float *x = buf[0], *xt = buf[1], *xn = buf[2], *xtn = buf[3];
+  hipLaunchKernelGGL((k_tri_prepare<WHICH>), dim3(d / 32, d / 32), dim3(256), 0, s, q, mneg, x, xt);
   hipLaunchKernelGGL((k_tri_diag_inverse<WHICH>), dim3(d / 128), dim3(128), 0, s, q, x, xt);
   AE_TRY(launch_status("tri_diag_inverse"));
   for (int b = 128; b < d; b *= 2) {
-    const int pairs = d / (2 * b);
-    const int64_t bb = (int64_t)b * b;
-    hipLaunchKernelGGL((k_tri_pack<WHICH>), dim3(lu_grid(pairs * bb)), dim3(256), 0, s, q, b, pairs, m21);
-    AE_TRY(launch_status("tri_pack"));
-    for (int p = 0; p < pairs; ++p) {
-      AE_TRY(dense_product(xt + (2 * p) * bb, m21 + p * bb, tt + p * bb, b, AE_F32, CONV_TRI_NONE, s));        // (M21 X11)^T
-      AE_TRY(dense_product(x + (2 * p + 1) * bb, tt + p * bb, x21 + p * bb, b, AE_F32, CONV_TRI_NONE, s));     // X22 M21 X11
-    }
-    hipLaunchKernelGGL(k_tri_assemble, dim3(2 * b / 32, 2 * b / 32, pairs), dim3(256), 0, s, (const float*)x, (const float*)x21, b, xn, xtn);
-    AE_TRY(launch_status("tri_assemble"));
-    float* t = x; x = xn; xn = t;
-    t = xt; xt = xtn; xtn = t;
+    ConvArgs a;
+    memset(&a, 0, sizeof(a));
+    a.n = d; a.hc = a.wc = 1; a.cin = a.cout = d; a.k = 1; a.up = 0; a.act = ACT_NONE; a.dtype = AE_F32;
+    a.tri_b = b;
+    a.x = xt; a.w = mneg; a.y = tt; a.tri = CONV_TRI_PAIR_UPPER_K0;       // T' = X11^T (-M21)^T = -(M21 X11)^T
+    AE_TRY(launch_conv_mfma(a, s));
+    a.x = x; a.w = tt; a.y = x; a.tri = CONV_TRI_PAIR_LOWER_K1;           // X21 = X22 T'^T (reads the diagonal blocks of x, writes below them)
+    AE_TRY(launch_conv_mfma(a, s));
+    a.x = tt; a.w = x; a.y = xt; a.tri = CONV_TRI_PAIR_UPPER_K1;          // X21^T = T' X22^T
+    AE_TRY(launch_conv_mfma(a, s));
   }
-  *res = x;
-  *res_t = xt;
   return AE_OK;
 }
 
@@ -470,7 +455,7 @@ extern "C" int model_lu_inverse_workspace(int64_t d, int64_t* bytes) {
   if (!bytes) return fail(AE_EINVAL, "model_lu_inverse_workspace: null argument");
   if (d < 128 || d > 16384 || d % 128 != 0 || ((d / 128) & (d / 128 - 1)) != 0)
     return fail(AE_EINVAL, "model_lu_inverse_workspace: d must be 128 times a power of two, at most 16384");
-  *bytes = (6 * d * d + 3 * (d * d / 4)) * 4 + 1024;
+  *bytes = 6 * d * d * 4 + 1024;
   return AE_OK;
 }
 
@@ -485,18 +470,17 @@ extern "C" int model_lu_inverse(const float* lp, const float* up, const float* l
   hipStream_t s = (hipStream_t)stream;
   const int64_t dd = d * d;
   float* f = reinterpret_cast<float*>(workspace);
-  float* const buf[4] = {f, f + dd, f + 2 * dd, f + 3 * dd};
-  float* linv_t = f + 4 * dd;                      // (L^-1)^T, kept while the upper factor is inverted
-  float* z = f + 5 * dd;                           // (U + diag s)^-1 L^-1
-  float* m21 = f + 6 * dd;                         // per level: sub-diagonal blocks, (M21 X11)^T, X22 M21 X11
-  float* tt = m21 + dd / 4;
-  float* x21 = tt + dd / 4;
+  float* mneg = f;                  // -M of the factor being inverted; afterwards (U + diag s)^-1 L^-1
+  float* tt = f + dd;               // scratch of the recursion
+  float* linv = f + 2 * dd;         // L^-1 and its transpose
+  float* linv_t = f + 3 * dd;
+  float* udinv_t = f + 4 * dd;      // ((U + diag s)^T)^-1 = ((U + diag s)^-1)^T and its transpose (U + diag s)^-1
+  float* udinv = f + 5 * dd;
   LuSrc q{lp, up, log_s, sign_s, nullptr, nullptr, (int)d};
-  float *res = nullptr, *res_t = nullptr;
-  AE_TRY(tri_inverse<0>(q, buf, m21, tt, x21, &res, &res_t, s));
-  AE_HIP(hipMemcpyAsync(linv_t, res_t, dd * 4, hipMemcpyDeviceToDevice, s));
-  AE_TRY(tri_inverse<1>(q, buf, m21, tt, x21, &res, &res_t, s));     // res = ((U + diag s)^T)^-1, res_t = (U + diag s)^-1
-  AE_TRY(dense_product(res_t, linv_t, z, (int)d, AE_F32, CONV_TRI_NONE, s));
+  AE_TRY(tri_inverse<0>(q, mneg, tt, linv, linv_t, s));
+  AE_TRY(tri_inverse<1>(q, mneg, tt, udinv_t, udinv, s));
+  float* z = mneg;
+  AE_TRY(dense_product(udinv, linv_t, z, (int)d, AE_F32, CONV_TRI_UPPER_LOWER, s));
   if (dtype == AE_BF16) hipLaunchKernelGGL((k_lu_inverse_out<bf16_t>), dim3(lu_grid(dd)), dim3(256), 0, s, (const float*)z, perm, (int)d, (bf16_t*)a_inv_out);
   else hipLaunchKernelGGL((k_lu_inverse_out<float>), dim3(lu_grid(dd)), dim3(256), 0, s, (const float*)z, perm, (int)d, (float*)a_inv_out);
   return launch_status("lu_inverse_out");

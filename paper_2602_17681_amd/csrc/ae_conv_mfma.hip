@@ -60,7 +60,12 @@ struct IgemmParams {
   //   1: x[m][k] = 0 for k > m and w[n][k] = 0 for k > n (lower times upper): K ends at min(last row, last column) + 1
   //   2: x[m][k] = 0 for k < m, wanted outputs n >= m: K starts at the tile's first row; tiles below the diagonal return
   //   3: w[n][k] = 0 for k < n, wanted outputs n < m: K starts at the tile's first column; tiles above the diagonal return
-  int tri;
+  //   4: x[m][k] = 0 for k < m and w[n][k] = 0 for k < n (upper times lower): K starts at max(first row, first column)
+  // Blocked triangular inverse, all pairs of neighbouring tri_b x tri_b diagonal blocks in one launch (tile sizes divide
+  // tri_b): only the tiles of one off-diagonal block per pair are computed, over the K range of one block:
+  //   8: tile rows in an even block r, columns in block r+1, K = block r;   10: the same tiles, K = block r+1;
+  //   9: tile rows in an odd block r, columns in block r-1, K = block r
+  int tri, tri_b;
 };
 
 // output row (pixel index in y) of GEMM row m
@@ -400,7 +405,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) __attribute__((amdgpu_waves_per_eu(
   int lb0 = xcd_logical_block((int)blockIdx.x, (int)gridDim.x);
   // triangular products: tile rows differ in work by an order of magnitude, so neighbouring tiles go to different
   // XCDs (the hardware's own round-robin) instead of one contiguous range per XCD, the longest K ranges first
-  if (p.tri != 0) lb0 = p.tri == 1 ? (int)gridDim.x - 1 - (int)blockIdx.x : (int)blockIdx.x;
+  if (p.tri != 0 && p.tri < 8) lb0 = p.tri == 1 ? (int)gridDim.x - 1 - (int)blockIdx.x : (int)blockIdx.x;
   int phase = 0;
   if (p.phases == 4) { phase = lb0 & 3; lb0 >>= 2; }   // the four phases of a tile run side by side: they read the same input
   const int split = INTERIOR ? 0 : lb0 / p.tiles_mn;
@@ -453,6 +458,13 @@ __global__ __launch_bounds__(WGM * WGN * 64) __attribute__((amdgpu_waves_per_eu(
   if (p.tri == 1) k_hi = (int)min((int64_t)p.K, min(m0 + BM, (int64_t)n0 + BN));
   else if (p.tri == 2) { if ((int64_t)n0 + BN <= m0) return; k_lo = (int)m0; }
   else if (p.tri == 3) { if ((int64_t)n0 >= m0 + BM) return; k_lo = n0; }
+  else if (p.tri == 4) k_lo = (int)max(m0, (int64_t)n0);
+  else if (p.tri >= 8) {
+    const int rb = (int)(m0 / p.tri_b), cb = n0 / p.tri_b;
+    if (p.tri == 9 ? !((rb & 1) == 1 && cb == rb - 1) : !((rb & 1) == 0 && cb == rb + 1)) return;
+    k_lo = (p.tri == 10 ? rb + 1 : rb) * p.tri_b;
+    k_hi = k_lo + p.tri_b;
+  }
   const int kt_lo = k_lo / BK, kt_hi = (k_hi + BK - 1) / BK;
   const int kt0 = INTERIOR ? kt_lo : max(kt_lo, split * p.slabs_per_split);   // first K slab of this workgroup
   int rs = (kt0 * BK) / p.Cin, ci0 = (kt0 * BK) % p.Cin;                // filter tap and first channel of the next slab to load
@@ -968,7 +980,10 @@ int launch_conv_mfma(const ConvArgs& a0, hipStream_t s) {
   p.Hv = a.hc; p.Wv = a.wc; p.stride = 1; p.pad = (a.k - 1) >> 1; p.phases = 1;
   p.resid = a0.resid;
   p.tri = a0.tri;
-  if (a0.tri != 0 && (a0.tri < 0 || a0.tri > 3 || a.k != 1 || a.hc != 1 || a.wc != 1 || a.up != 0 || a.n != a.cout || a.cin != a.cout ||
+  p.tri_b = a0.tri_b;
+  if (a0.tri >= 8 && (a0.tri > 10 || a.dtype != AE_F32 || a0.tri_b < 128 || a0.tri_b % 128 != 0 || a.n % (2 * a0.tri_b) != 0))
+    return fail(AE_EINVAL, "conv_mfma: bad block size for the blocked triangular inverse");
+  if (a0.tri != 0 && (a0.tri < 0 || (a0.tri > 4 && a0.tri < 8) || a0.tri > 10 || a.k != 1 || a.hc != 1 || a.wc != 1 || a.up != 0 || a.n != a.cout || a.cin != a.cout ||
                       a0.epi != CONV_EPI_NONE || a.partial))
     return fail(AE_EINVAL, "conv_mfma: triangular K ranges are for square dense products only");
   p.x_bytes = (unsigned)((int64_t)a.n * (a.hc >> a.up) * (a.wc >> a.up) * a.cin * es);

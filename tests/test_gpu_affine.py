@@ -174,6 +174,17 @@ def test_inverse_matches_the_inverse_of_the_composed_matrix(ae, d, kind, dtype):
         assert np.abs(a @ got - np.eye(d)).max() < 1e-4
 
 
+def test_inverse_full_size(ae):
+    """d = 4 096, bf16 output: the size bench.py times beside the parametrisation step."""
+    d = 4096
+    params = wl.make_lu_params(d, seed=11, kind="bd_hadamard", noise=1e-3)
+    a = ao.lu_compose(*params)
+    got = _inverse(ae, params, d, "bf16")
+    assert _close(got, np.linalg.inv(a), TOL["bf16"])
+    got32 = _inverse(ae, params, d, "f32")
+    assert np.abs(a @ got32 - np.eye(d)).max() < 1e-4
+
+
 def test_inverse_feeds_the_transformation_error(ae):
     """The whole chain on the GPU: parameters -> A and A^-1 -> E(T), against the oracle chain with numpy's inverse."""
     import torch
@@ -206,7 +217,7 @@ def test_inverse_argument_checks(ae):
     n = C.c_int64()
     assert ae.lib.model_lu_inverse_workspace(384, C.byref(n)) == -1        # 3 blocks: not a power of two
     assert ae.lib.model_lu_inverse_workspace(64, C.byref(n)) == -1
-    assert ae.lib.model_lu_inverse_workspace(256, C.byref(n)) == 0 and n.value == (6 * 256 * 256 + 3 * 256 * 256 // 4) * 4 + 1024
+    assert ae.lib.model_lu_inverse_workspace(256, C.byref(n)) == 0 and n.value == 6 * 256 * 256 * 4 + 1024
     assert ae.lib.model_lu_inverse(p, p, p, p, p, 384, 0, p, p, None) == -1
     assert ae.lib.model_lu_inverse(p, p, p, p, p, 128, 3, p, p, None) == -1
     assert ae.lib.model_lu_inverse(None, p, p, p, p, 128, 0, p, p, None) == -1
