@@ -392,7 +392,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) __attribute__((amdgpu_waves_per_eu(
   constexpr int MI = WM / 32, NJ = WN / 32;     // 32x32 MFMA tiles per wave
   constexpr int A_CHUNKS = BM / RSTEP, B_CHUNKS = BN / RSTEP;
   constexpr int SW = WN + 16 / ES;              // staging row stride of the epilogue (elements): +16 bytes
-  constexpr int NSTAGE = DMA ? 3 : 2;
+  constexpr int NSTAGE = DMA ? (NT == 512 ? 4 : 3) : 2;   // eight wavefronts: one workgroup per compute unit, LDS for a fourth stage
   constexpr int SLAB_BYTES = NSTAGE * (BM + BN) * BKB;
   constexpr int STAGE_BYTES = (NT / 64) * 32 * SW * ES;
   __shared__ __attribute__((aligned(16))) char smem[SLAB_BYTES > STAGE_BYTES ? SLAB_BYTES : STAGE_BYTES];
@@ -549,19 +549,21 @@ __global__ __launch_bounds__(WGM * WGN * 64) __attribute__((amdgpu_waves_per_eu(
     const unsigned lds_b = (unsigned)(size_t)(lds_char*)sB + (unsigned)(wn * WN * BKB);
     IGEMM_DMA(0);
     if (KT > 1) IGEMM_DMA(1);
-    int cur = 0, nxt = 2;
+    if constexpr (NSTAGE == 4) { if (KT > 2) IGEMM_DMA(2); }
+    int cur = 0, nxt = NSTAGE - 1;
     for (int kt = 0; kt < KT; ++kt) {
-      // vmcnt(n): at most n of this wave's loads outstanding (they complete in order);
+      // vmcnt(n): at most n of this wave's loads outstanding (they complete in order): the slabs issued after slab kt;
       // the other counters are left alone (expcnt 7, lgkmcnt 15)
-      if (kt + 1 < KT) __builtin_amdgcn_s_waitcnt((L & 15) | ((L >> 4) << 14) | 0x0F70);
+      if (NSTAGE == 4 && kt + 2 < KT) __builtin_amdgcn_s_waitcnt(((2 * L) & 15) | (((2 * L) >> 4) << 14) | 0x0F70);
+      else if (kt + 1 < KT) __builtin_amdgcn_s_waitcnt((L & 15) | ((L >> 4) << 14) | 0x0F70);
       else __builtin_amdgcn_s_waitcnt(0x0F70);
       __builtin_amdgcn_s_barrier();
       uint4v fa[KS][MI], fb[KS][NJ];
       SlabReads<0, KS, MI, NJ, BKB>::run(fa, fb, lds_a + (unsigned)(cur * BM * BKB), lds_b + (unsigned)(cur * BN * BKB), lane_off);
-      if (kt + 2 < KT) IGEMM_DMA(nxt);
+      if (kt + NSTAGE - 1 < KT) IGEMM_DMA(nxt);
       SlabSteps<T, KS, 0, MI, NJ>::run(fa, fb, acc);
-      cur = cur == 2 ? 0 : cur + 1;
-      nxt = nxt == 2 ? 0 : nxt + 1;
+      cur = cur == NSTAGE - 1 ? 0 : cur + 1;
+      nxt = nxt == NSTAGE - 1 ? 0 : nxt + 1;
     }
 #undef IGEMM_DMA
     __syncthreads();                             // every wave is done with the slabs: the epilogue reuses the memory
@@ -693,7 +695,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
   constexpr int ES = (int)sizeof(T);
   constexpr int BM = 256, BKB = 64;
-  constexpr int BK = BKB / ES;
   constexpr int TH = BM / W, PW = W + 2, PC = (TH + 2) * PW;
   constexpr int PASSES = patch_passes(W);
   constexpr int PATCH_BYTES = PASSES * 4096;
@@ -1037,11 +1038,7 @@ int launch_conv_mfma(const ConvArgs& a0, hipStream_t s) {
     if (interior) hipLaunchKernelGGL((k_igemm<T, BMV, BNV, GM, GN, KB, true, true>), grid, dim3(256), 0, s, p); \
     else hipLaunchKernelGGL((k_igemm<T, BMV, BNV, GM, GN, KB, false, true>), grid, dim3(256), 0, s, p); \
   } while (0)
-#define IGEMM_LAUNCH_T(T, BMV, BNV, GM, GN)                                                            \
-  do {                                                                                                 \
-    if (t.bkb == 128) IGEMM_LAUNCH_K(T, BMV, BNV, GM, GN, 128);                                        \
-    else IGEMM_LAUNCH_K(T, BMV, BNV, GM, GN, 64);                                                      \
-  } while (0)
+#define IGEMM_LAUNCH_T(T, BMV, BNV, GM, GN) IGEMM_LAUNCH_K(T, BMV, BNV, GM, GN, 64)   /* pick_tile: 64-byte slabs only */
 #define IGEMM_LAUNCH(BMV, BNV, GM, GN)                                         \
   do {                                                                         \
     if (a.dtype == AE_BF16) IGEMM_LAUNCH_T(bf16_t, BMV, BNV, GM, GN);          \
@@ -1592,8 +1589,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[s_][i][e] = 0.0f;
 
-  TrFrag fa0[MI], fb0[3], fa1[MI], fb1[3];
-  constexpr int NR = 2 * (MI + 3);               // LDS reads per K-step
+  [[maybe_unused]] TrFrag fa0[MI], fb0[3], fa1[MI], fb1[3];   // (used by the device pass only)
+  [[maybe_unused]] constexpr int NR = 2 * (MI + 3);            // LDS reads per K-step
 #define WGRAD3_MMA(FA, FB)                                                                                   \
   {                                                                                                          \
     bf16x8 av[MI];                                                                                           \
@@ -1625,11 +1622,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
     __builtin_amdgcn_s_barrier();
     const int nxt = cur == 2 ? 0 : cur + 1;
     if (t + 2 < KT) { const int st2 = nxt == 2 ? 0 : nxt + 1; WGRAD3_DMA(st2); }
-    const unsigned sa = lds0 + (unsigned)(cur * G::STAGE) + a_lane;
+    [[maybe_unused]] const unsigned sa = lds0 + (unsigned)(cur * G::STAGE) + a_lane;
     unsigned sb[3], nb[3];
 #pragma unroll
     for (int s_ = 0; s_ < 3; ++s_) { sb[s_] = lds0 + (unsigned)(cur * G::STAGE) + b_lane[s_]; nb[s_] = lds0 + (unsigned)(nxt * G::STAGE) + b_lane[s_]; }
-    const unsigned na = lds0 + (unsigned)(nxt * G::STAGE) + a_lane;
+    [[maybe_unused]] const unsigned na = lds0 + (unsigned)(nxt * G::STAGE) + a_lane;
 #if defined(__HIP_DEVICE_COMPILE__)
     wgrad3_reads<BM, SW, 1>(fa1, fb1, sa, sb);
     LGKM_WAIT(NR);
