@@ -422,6 +422,13 @@ __global__ __launch_bounds__(WGM * WGN * 64) __attribute__((amdgpu_waves_per_eu(
     tile_n = lb / tiles_m;
     tile_m = lb - tile_n * tiles_m;
   }
+  if (p.tri >= 8) {                             // only the tiles of one off-diagonal block per pair are launched
+    const int tbm = p.tri_b / BM, tbn = p.tri_b / BN, per_pair = tbm * tbn;
+    const int pair = lb / per_pair, in_pair = lb - pair * per_pair;
+    const int tr = in_pair / tbn, tc = in_pair - tr * tbn;
+    tile_m = (2 * pair + (p.tri == 9 ? 1 : 0)) * tbm + tr;
+    tile_n = (2 * pair + (p.tri == 9 ? 0 : 1)) * tbn + tc;
+  }
   const int64_t m0 = tile_m * BM;
   const int n0 = tile_n * BN;
   const int pad_h = p.pad - (phase >> 1), pad_w = p.pad - (phase & 1);
@@ -1031,6 +1038,7 @@ int launch_conv_mfma(const ConvArgs& a0, hipStream_t s) {
   splits = (KT + p.slabs_per_split - 1) / p.slabs_per_split;
   p.split_out = splits > 1 ? a.splitk_ws : nullptr;
   dim3 grid((unsigned)(tiles_m * p.tiles_n * splits * p.phases));
+  if (a0.tri >= 8) grid = dim3((unsigned)((p.M / (2 * a0.tri_b)) * (a0.tri_b / t.bm) * (a0.tri_b / t.bn)));
   const bool interior = splits == 1 && p.M % t.bm == 0 && p.N % t.bn == 0 && !a.y_aux && a.act != ACT_SIGMOID &&
                         !(a.partial && a.act != ACT_NONE);
 #define IGEMM_LAUNCH_K(T, BMV, BNV, GM, GN, KB)                                                        \
