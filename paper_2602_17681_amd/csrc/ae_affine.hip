@@ -251,36 +251,65 @@ __global__ __launch_bounds__(256) void k_tri_prepare(LuSrc q, float* __restrict_
   }
 }
 
-// X_bb = M_bb^-1 for every 128 x 128 diagonal block b (one workgroup each): thread j solves column j by forward
-// substitution; the block and its transpose are written into the full matrices x and xt.
+// X_bb = M_bb^-1 for every 128 x 128 diagonal block b (one workgroup of 256 threads each), the same recursion inside
+// LDS: 16 x 16 diagonal blocks by forward substitution (thread j solves column j of its block), then three levels
+// of merges [[X11, 0], [-X22 M21 X11, X22]] with all threads sharing the outputs of the two small products.  The
+// block and its transpose are written into the full matrices x and xt.
 template <int WHICH>
-__global__ __launch_bounds__(128) void k_tri_diag_inverse(LuSrc q, float* __restrict__ x, float* __restrict__ xt) {
+__global__ __launch_bounds__(256) void k_tri_diag_inverse(LuSrc q, float* __restrict__ x, float* __restrict__ xt) {
   __shared__ float mb[128][129];
   __shared__ float xb[128][129];
-  const int b = blockIdx.x, j = threadIdx.x, o = b * 128;
-  for (int i = 0; i < 128; ++i) mb[i][j] = tri_elem<WHICH>(q, o + i, o + j);
-  __syncthreads();
-  for (int i = 0; i < 128; ++i) {
-    float v = 0.0f;
-    if (i == j) {
-      v = 1.0f / mb[j][j];
-    } else if (i > j) {
-      // column j of xb is this thread's own; four independent partial sums keep the LDS reads in flight
-      float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
-      int k = j;
-      for (; k + 4 <= i; k += 4) {
-        a0 = fmaf(mb[i][k], xb[k][j], a0);
-        a1 = fmaf(mb[i][k + 1], xb[k + 1][j], a1);
-        a2 = fmaf(mb[i][k + 2], xb[k + 2][j], a2);
-        a3 = fmaf(mb[i][k + 3], xb[k + 3][j], a3);
-      }
-      for (; k < i; ++k) a0 = fmaf(mb[i][k], xb[k][j], a0);
-      v = -((a0 + a1) + (a2 + a3)) / mb[i][i];
-    }
-    xb[i][j] = v;
+  __shared__ float tb[64 * 64];                        // M21 X11 of every pair of the current level: pairs * b * b = 64 b values
+  const int blk = blockIdx.x, tid = threadIdx.x, o = blk * 128;
+  for (int e = tid; e < 128 * 128; e += 256) {
+    const int i = e >> 7, j = e & 127;
+    mb[i][j] = tri_elem<WHICH>(q, o + i, o + j);
+    xb[i][j] = 0.0f;
   }
   __syncthreads();
-  for (int i = 0; i < 128; ++i) {
+  if (tid < 128) {                                     // column tid of its 16 x 16 diagonal block
+    const int j = tid, b0 = j & ~15;
+    for (int i = j; i < b0 + 16; ++i) {
+      float acc = 0.0f;
+      for (int k = j; k < i; ++k) acc = fmaf(mb[i][k], xb[k][j], acc);
+      xb[i][j] = i == j ? 1.0f / mb[j][j] : -acc / mb[i][i];
+    }
+  }
+  __syncthreads();
+  for (int b = 16; b < 128; b *= 2) {
+    const int lb = b == 16 ? 4 : (b == 32 ? 5 : 6);    // log2 b
+    // T[p][r][c] = sum_k M21[r][k] X11[k][c], X11 lower triangular: k >= c
+    for (int e = tid; e < 64 * b; e += 256) {
+      const int p = e >> (2 * lb), r = (e >> lb) & (b - 1), c = e & (b - 1);
+      const int r1 = (2 * p + 1) * b + r, c0 = 2 * p * b;
+      float a0 = 0.0f, a1 = 0.0f;
+      int k = c;
+      for (; k + 2 <= b; k += 2) {
+        a0 = fmaf(mb[r1][c0 + k], xb[c0 + k][c0 + c], a0);
+        a1 = fmaf(mb[r1][c0 + k + 1], xb[c0 + k + 1][c0 + c], a1);
+      }
+      if (k < b) a0 = fmaf(mb[r1][c0 + k], xb[c0 + k][c0 + c], a0);
+      tb[e] = a0 + a1;
+    }
+    __syncthreads();
+    // X21[r][c] = -sum_k X22[r][k] T[k][c], X22 lower triangular: k <= r
+    for (int e = tid; e < 64 * b; e += 256) {
+      const int p = e >> (2 * lb), r = (e >> lb) & (b - 1), c = e & (b - 1);
+      const int r1 = (2 * p + 1) * b, c0 = 2 * p * b;
+      const float* t = tb + (p << (2 * lb));
+      float a0 = 0.0f, a1 = 0.0f;
+      int k = 0;
+      for (; k + 2 <= r + 1; k += 2) {
+        a0 = fmaf(xb[r1 + r][r1 + k], t[(k << lb) + c], a0);
+        a1 = fmaf(xb[r1 + r][r1 + k + 1], t[((k + 1) << lb) + c], a1);
+      }
+      if (k <= r) a0 = fmaf(xb[r1 + r][r1 + k], t[(k << lb) + c], a0);
+      xb[r1 + r][c0 + c] = -(a0 + a1);               // (below the diagonal blocks: nobody reads it in this pass)
+    }
+    __syncthreads();
+  }
+  for (int e = tid; e < 128 * 128; e += 256) {
+    const int i = e >> 7, j = e & 127;
     x[(int64_t)(o + i) * q.d + o + j] = xb[i][j];
     xt[(int64_t)(o + i) * q.d + o + j] = xb[j][i];
   }
@@ -347,7 +376,7 @@ template <int WHICH>
 int tri_inverse(const LuSrc& q, float* mneg, float* tt, float* x, float* xt, hipStream_t s) {
   const int d = q.d;
   hipLaunchKernelGGL((k_tri_prepare<WHICH>), dim3(d / 32, d / 32), dim3(256), 0, s, q, mneg, x, xt);
-  hipLaunchKernelGGL((k_tri_diag_inverse<WHICH>), dim3(d / 128), dim3(128), 0, s, q, x, xt);
+  hipLaunchKernelGGL((k_tri_diag_inverse<WHICH>), dim3(d / 128), dim3(256), 0, s, q, x, xt);
   AE_TRY(launch_status("tri_diag_inverse"));
   for (int b = 128; b < d; b *= 2) {
     ConvArgs a;
