@@ -56,3 +56,42 @@ def vol_penalty(log_s):
     """The form used in practice: (sum_i log|s_i|)^2 and its gradient with respect to log|s|."""
     t = float(np.sum(np.asarray(log_s, dtype=np.float64)))
     return t * t, np.full(np.shape(log_s), 2.0 * t)
+
+
+# ---- QR parametrisation (Eq. 5):  Q = exp((G - G^T) / 2),  A = Q (R + diag(s)) ------------------------------------
+# G: full d x d array of free parameters; Rp: full d x d array of which the strictly upper part is used; s as above.
+# The matrix exponential and its Frechet derivative are library routines (scipy.linalg), used as single steps.
+
+def qr_factors(G, Rp, log_s, sign):
+    """Q (orthogonal, determinant +1), R + diag(s) (upper triangular) and s of Eq. 5."""
+    import scipy.linalg
+    G = np.asarray(G, dtype=np.float64)
+    s = np.asarray(sign, dtype=np.float64) * np.exp(np.asarray(log_s, dtype=np.float64))
+    S = 0.5 * (G - G.T)
+    Q = scipy.linalg.expm(S)
+    RD = np.triu(np.asarray(Rp, dtype=np.float64), 1) + np.diag(s)
+    return Q, RD, s
+
+
+def qr_compose(G, Rp, log_s, sign):
+    """A = Q (R + diag(s)), Eq. 5."""
+    Q, RD, _ = qr_factors(G, Rp, log_s, sign)
+    return Q @ RD
+
+
+def qr_gradients(dA, G, Rp, log_s, sign):
+    """Gradients of a scalar loss with respect to G, the strictly upper part of R and log|s|, given dA = d loss / d A.
+    d/d(R + diag s) = Q^T dA; d/dQ = dA (R + diag s)^T; the exponential's adjoint maps d/dQ to d/dS =
+    L_exp(S^T, d/dQ) (the Frechet derivative of exp at S^T in the direction d/dQ); S = (G - G^T)/2 gives
+    d/dG = (d/dS - (d/dS)^T) / 2."""
+    import scipy.linalg
+    dA = np.asarray(dA, dtype=np.float64)
+    Q, RD, s = qr_factors(G, Rp, log_s, sign)
+    dRD = Q.T @ dA
+    dR = np.triu(dRD, 1)
+    dlog_s = np.diag(dRD) * s
+    dQ = dA @ RD.T
+    S = 0.5 * (np.asarray(G, dtype=np.float64) - np.asarray(G, dtype=np.float64).T)
+    dS = scipy.linalg.expm_frechet(S.T, dQ, compute_expm=False)
+    dG = 0.5 * (dS - dS.T)
+    return dG, dR, dlog_s

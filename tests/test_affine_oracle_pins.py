@@ -99,3 +99,58 @@ def test_initialisation_is_block_diagonal_hadamard_and_noise_stays_small():
     a2 = ao.lu_compose(lp2, up2, ls2, sg2, perm2)
     assert np.array_equal(perm, perm2) and np.array_equal(ls, ls2)
     assert 0 < np.abs(a2 - a).max() < 0.05 and np.allclose(a2[~off], a[~off], atol=2e-3)
+
+
+# ------------------------------------------------------------------ QR parametrisation (Eq. 5)
+def _qr_params(d, seed, **kw):
+    return [a.astype(np.float64) for a in wl.make_qr_params(d, seed, **kw)]
+
+
+def test_qr_two_by_two_is_a_plane_rotation():
+    th = 0.7
+    g = np.array([[5.0, 2 * th], [0.0, -3.0]])               # the symmetric part of G does not matter: S = [[0, th], [-th, 0]]
+    a = ao.qr_compose(g, np.array([[9.0, 0.5], [9.0, 9.0]]), np.log([2.0, 3.0]), [1.0, -1.0])
+    q = np.array([[np.cos(th), np.sin(th)], [-np.sin(th), np.cos(th)]])
+    assert np.allclose(a, q @ np.array([[2.0, 0.5], [0.0, -3.0]]), rtol=1e-13)
+
+
+def test_qr_factor_is_a_rotation_and_the_determinant_is_the_product_of_s():
+    g, rp, ls, sg = _qr_params(40, 1)
+    Q, RD, s = ao.qr_factors(g, rp, ls, sg)
+    assert np.allclose(Q.T @ Q, np.eye(40), atol=1e-12) and np.isclose(np.linalg.det(Q), 1.0)
+    assert np.array_equal(np.tril(RD, -1), np.zeros((40, 40))) and np.allclose(np.diag(RD), s)
+    sign, logdet = np.linalg.slogdet(ao.qr_compose(g, rp, ls, sg))
+    assert np.isclose(logdet, ls.sum(), atol=1e-10) and sign == np.prod(sg)
+    sym = g + g.T                                             # a symmetric G gives Q = I: A is upper triangular
+    assert np.allclose(ao.qr_compose(sym, rp, ls, sg), RD, atol=1e-13)
+
+
+def test_qr_gradients_against_finite_differences():
+    d = 5
+    g, rp, ls, sg = _qr_params(d, 2)
+    g *= 3.0                                                  # a rotation well away from the identity
+    c = np.random.default_rng(0).standard_normal((d, d))
+    loss = lambda g_, rp_, ls_: float(np.sum(c * np.tanh(ao.qr_compose(g_, rp_, ls_, sg))))
+    a = ao.qr_compose(g, rp, ls, sg)
+    dg, dr, dls = ao.qr_gradients(c * (1.0 - np.tanh(a) ** 2), g, rp, ls, sg)
+    h = 1e-6
+    for i in range(d):
+        for j in range(d):
+            e = np.zeros((d, d)); e[i, j] = h
+            assert abs((loss(g + e, rp, ls) - loss(g - e, rp, ls)) / (2 * h) - dg[i, j]) < 1e-7
+            assert abs((loss(g, rp + e, ls) - loss(g, rp - e, ls)) / (2 * h) - dr[i, j]) < 1e-7
+        e = np.zeros(d); e[i] = h
+        assert abs((loss(g, rp, ls + e) - loss(g, rp, ls - e)) / (2 * h) - dls[i]) < 1e-7
+    assert np.allclose(dg, -dg.T) and np.array_equal(np.tril(dr), np.zeros((d, d)))     # only the skew part of G acts
+
+
+def test_qr_initialisation_is_block_diagonal_orthogonal():
+    d, b = 96, 32
+    g, rp, ls, sg = _qr_params(d, 3, kind="bd_orthogonal")
+    a = ao.qr_compose(g, rp, ls, sg)
+    off = np.kron(np.eye(d // b), np.ones((b, b))) == 0
+    assert np.allclose(a @ a.T, np.eye(d), atol=1e-5) and np.abs(a[off]).max() < 1e-6
+    assert np.abs(a[~off]).max() > 0.2 and ao.vol_penalty(ls)[0] == 0.0
+    g2, rp2, _, _ = _qr_params(d, 3, kind="bd_orthogonal", noise=1e-3)
+    a2 = ao.qr_compose(g2, rp2, ls, sg)
+    assert 0 < np.abs(a2 - a).max() < 0.05

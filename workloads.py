@@ -261,3 +261,37 @@ def make_lu_params(d, seed, kind="random", noise=0.0, block=32):
             up += noise * rng.standard_normal((d, d)) * off
     f = lambda a: np.ascontiguousarray(a, dtype=np.float32)
     return f(lp), f(up), f(log_s), f(sign), perm
+
+
+def make_qr_params(d, seed, kind="random", noise=0.0, block=32):
+    """Free parameters of the QR parametrisation A = exp((G - G^T)/2) (R + diag(s)): (G, Rp, log_s, sign), float32.
+    kind "random": dense Gaussian G and R of size 1/sqrt(d), log|s| ~ N(0, 0.3), random signs.
+    kind "bd_orthogonal": the paper's initialisation for this parametrisation — A is block diagonal with blocks of
+    `block` x `block` random rotations (each block's G is the real skew-symmetric logarithm of the rotation, a
+    library routine; R = 0, s = 1); `noise` > 0 adds Gaussian noise of that size to G and R outside the diagonal
+    blocks."""
+    rng = np.random.default_rng([seed, 0x9A7])
+    if kind == "random":
+        g = rng.standard_normal((d, d)) / np.sqrt(d)
+        rp = rng.standard_normal((d, d)) / np.sqrt(d)
+        log_s = 0.3 * rng.standard_normal(d)
+        sign = rng.choice([-1.0, 1.0], size=d)
+    else:
+        import scipy.linalg
+        assert d % block == 0
+        g, rp = np.zeros((d, d)), np.zeros((d, d))
+        log_s, sign = np.zeros(d), np.ones(d)
+        for b in range(d // block):
+            q, r = np.linalg.qr(rng.standard_normal((block, block)))
+            q = q * np.sign(np.diag(r))[None, :]
+            if np.linalg.det(q) < 0:
+                q[:, 0] = -q[:, 0]                                   # a rotation: determinant +1, so a real logarithm exists
+            lg = np.real(scipy.linalg.logm(q))
+            o = b * block
+            g[o:o + block, o:o + block] = 0.5 * (lg - lg.T)
+        if noise > 0.0:
+            off = np.kron(np.eye(d // block), np.ones((block, block))) == 0
+            g += noise * rng.standard_normal((d, d)) * off
+            rp += noise * rng.standard_normal((d, d)) * off
+    f = lambda a: np.ascontiguousarray(a, dtype=np.float32)
+    return f(g), f(rp), f(log_s), f(sign)
