@@ -243,6 +243,24 @@ int model_lu_inverse(const float* lp, const float* up, const float* log_s, const
  * stream and waited for, so the calls become synchronous. */
 int model_lu_timing(int enable, double* gemm_ms, int64_t* launches);
 
+/* QR parametrisation of a learnable invertible matrix (Eq. 5 of the same section):
+ *     Q = exp((G - G^T) / 2),   A = Q (R + diag(s)).
+ * Free parameters (device, binary32 master copies): g [d][d] (only its skew-symmetric part acts), rp [d][d] of which
+ * the strictly upper part is read, log_s, sign_s [d] as for the LU form.  The exponential is scaling and squaring
+ * in binary32 on the matrix cores: X = S / 2^squarings, a Taylor polynomial of order 10 in Horner form, then
+ * `squarings` squarings; choose squarings with 2^squarings >= 2 ||S||_2 (5 covers ||S|| <= 16; 0 .. 16 accepted).
+ * d: a multiple of 32, 32..16384.  workspace: model_qr_workspace bytes ((18 + 2 squarings) d x d binary32 matrices),
+ * 16-byte aligned like every [d][d] array.
+ * model_qr_compose   writes a_out = A [d][d] in dtype and leaves the intermediate matrices in the workspace.
+ * model_qr_backward  given g_a = dLoss/dA [d][d] in dtype and THE SAME workspace, untouched since model_qr_compose
+ *   ran on the same parameters, writes d_g [d][d] (skew-symmetric), d_rp [d][d] (strictly upper part, zero
+ *   elsewhere) and d_log_s [d] in binary32. */
+int model_qr_workspace(int64_t d, int squarings, int64_t* bytes);
+int model_qr_compose(const float* g, const float* rp, const float* log_s, const float* sign_s, int64_t d, int dtype,
+                     int squarings, void* a_out, void* workspace, void* stream);
+int model_qr_backward(const void* g_a, const float* rp, const float* log_s, const float* sign_s, int64_t d, int dtype,
+                      int squarings, float* d_g, float* d_rp, float* d_log_s, void* workspace, void* stream);
+
 /* Folding of affine transformations T(x) = A x + v into a linear layer f(x) = W x + b (the paper's appendix
  * "Folding & Transformation Structure"): the layer x -> T_l(f(T_r^-1(x))) has
  *     w_out = A_l W A_r^-1 ,   b_out = A_l b - w_out v_r + v_l .

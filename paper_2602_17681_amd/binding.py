@@ -23,7 +23,7 @@ SYMBOLS = [
     "model_set_sample_offset", "model_forward", "model_backward", "model_loss_mse", "model_noise",
     "model_pnorm_awgn", "model_gen_bits", "model_count_errors", "model_num_steps", "model_step_info",
     "model_get_activation", "model_timing_enable", "model_set_overlap", "model_calibrate_mfma", "model_mx_quantize", "model_transform_mse_workspace",
-    "model_transform_mse", "model_lu_workspace", "model_lu_compose", "model_lu_backward", "model_vol_penalty", "model_lu_inverse_workspace", "model_lu_inverse", "model_lu_timing", "model_fold_workspace", "model_fold_linear", "model_fold_embedding", "model_timing_slots",
+    "model_transform_mse", "model_lu_workspace", "model_lu_compose", "model_lu_backward", "model_vol_penalty", "model_lu_inverse_workspace", "model_lu_inverse", "model_lu_timing", "model_qr_workspace", "model_qr_compose", "model_qr_backward", "model_fold_workspace", "model_fold_linear", "model_fold_embedding", "model_timing_slots",
     "model_timing_read", "model_timing_reset", "model_last_error",
 ]
 
@@ -70,6 +70,9 @@ def _load():
     L.model_lu_timing.argtypes = [C.c_int, C.POINTER(C.c_double), i64p]
     L.model_lu_inverse_workspace.argtypes = [C.c_int64, i64p]
     L.model_lu_inverse.argtypes = [vp, vp, vp, vp, vp, C.c_int64, C.c_int, vp, vp, vp]
+    L.model_qr_workspace.argtypes = [C.c_int64, C.c_int, i64p]
+    L.model_qr_compose.argtypes = [vp, vp, vp, vp, C.c_int64, C.c_int, C.c_int, vp, vp, vp]
+    L.model_qr_backward.argtypes = [vp, vp, vp, vp, C.c_int64, C.c_int, C.c_int, vp, vp, vp, vp, vp]
     L.model_fold_workspace.argtypes = [C.c_int64, C.c_int64, C.c_int64, C.c_int64, C.c_int, i64p]
     L.model_fold_linear.argtypes = [vp, vp, C.c_int64, C.c_int64, vp, C.c_int64, vp, vp, C.c_int64, vp, C.c_int, vp, vp, vp, vp]
     L.model_fold_embedding.argtypes = [vp, C.c_int64, C.c_int64, vp, vp, C.c_int, vp, vp]
@@ -296,6 +299,29 @@ def model_lu_timing(enable):
     ms, n = C.c_double(0.0), C.c_int64(0)
     _check(lib.model_lu_timing(1 if enable else 0, C.byref(ms), C.byref(n)))
     return ms.value, n.value
+
+
+def model_qr_workspace(d, squarings=5):
+    n = C.c_int64()
+    _check(lib.model_qr_workspace(d, squarings, C.byref(n)))
+    return n.value
+
+
+def model_qr_compose(g, rp, log_s, sign_s, d, a_out, workspace, squarings=5):
+    dtype = AE_BF16 if a_out.dtype == torch.bfloat16 else AE_F32
+    assert g.numel() == d * d and rp.numel() == d * d and log_s.numel() == d and sign_s.numel() == d and a_out.numel() == d * d
+    assert workspace.numel() * workspace.element_size() >= model_qr_workspace(d, squarings)
+    _check(lib.model_qr_compose(_ptr(g, torch.float32), _ptr(rp, torch.float32), _ptr(log_s, torch.float32), _ptr(sign_s, torch.float32),
+                                d, dtype, squarings, _ptr(a_out), _ptr(workspace), _stream()))
+
+
+def model_qr_backward(g_a, rp, log_s, sign_s, d, d_g, d_rp, d_log_s, workspace, squarings=5):
+    dtype = AE_BF16 if g_a.dtype == torch.bfloat16 else AE_F32
+    assert g_a.numel() == d * d and rp.numel() == d * d and d_g.numel() == d * d and d_rp.numel() == d * d and d_log_s.numel() == d
+    assert workspace.numel() * workspace.element_size() >= model_qr_workspace(d, squarings)
+    _check(lib.model_qr_backward(_ptr(g_a), _ptr(rp, torch.float32), _ptr(log_s, torch.float32), _ptr(sign_s, torch.float32), d, dtype,
+                                 squarings, _ptr(d_g, torch.float32), _ptr(d_rp, torch.float32), _ptr(d_log_s, torch.float32),
+                                 _ptr(workspace), _stream()))
 
 
 def model_fold_workspace(out, in_, p, q, dtype):

@@ -393,6 +393,88 @@ int tri_inverse(const LuSrc& q, float* mneg, float* tt, float* x, float* xt, hip
   return AE_OK;
 }
 
+// ---- QR parametrisation (Eq. 5):  Q = exp((G - G^T) / 2),  A = Q (R + diag s) ------------------------------------
+// The exponential is scaling and squaring: X = S / 2^J, a Taylor polynomial of order M in Horner form
+// (H_M = I + X/M, H_k = I + X H_{k+1} / k), then J squarings — all binary32 products on the matrix cores
+// (y = x w^T, so every product needs the transpose of its right factor: one fused element-wise pass per step
+// writes a result and its transpose).  The backward pass walks the same chain in reverse with the stored H_k, Q_i.
+constexpr int kQrOrder = 10;
+
+// out = ident * I + alpha * y (+ beta * y2), out_t = out^T; 32 x 32 tiles.  y2, out, out_t may be null.
+__global__ __launch_bounds__(256) void k_qr_combine(const float* __restrict__ y, const float* __restrict__ y2, float alpha, float beta,
+                                                    float ident, int d, float* __restrict__ out, float* __restrict__ out_t) {
+  __shared__ float tile[32][33];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int r = r0 + ty + 8 * j, c = c0 + tx;
+    const int64_t i = (int64_t)r * d + c;
+    float v = alpha * y[i] + (r == c ? ident : 0.0f);
+    if (y2) v += beta * y2[i];
+    if (out) out[i] = v;
+    tile[ty + 8 * j][tx] = v;
+  }
+  __syncthreads();
+  if (out_t) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) out_t[(int64_t)(c0 + ty + 8 * j) * d + r0 + tx] = tile[tx][ty + 8 * j];
+  }
+}
+
+// out = scale * (g - g^T): the scaled skew part (scale = 1 / (2 * 2^J) forward; the same form gives dG from dX)
+__global__ __launch_bounds__(256) void k_qr_skew(const float* __restrict__ g, float scale, int d, float* __restrict__ out) {
+  __shared__ float tile[32][33];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) tile[ty + 8 * j][tx] = g[(int64_t)(c0 + ty + 8 * j) * d + r0 + tx];   // g[c][r]
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int r = r0 + ty + 8 * j, c = c0 + tx;
+    out[(int64_t)r * d + c] = scale * (g[(int64_t)r * d + c] - tile[tx][ty + 8 * j]);
+  }
+}
+
+// acc = (first ? 0 : acc) + alpha * y
+__global__ __launch_bounds__(256) void k_qr_axpy(float* __restrict__ acc, const float* __restrict__ y, float alpha, int first, int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256)
+    acc[i] = (first ? 0.0f : acc[i]) + alpha * y[i];
+}
+
+// binary32 <-> storage type
+template <typename T>
+__global__ __launch_bounds__(256) void k_to_f32(const T* __restrict__ in, float* __restrict__ out, int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) out[i] = Store<T>::ld(in + i);
+}
+template <typename T>
+__global__ __launch_bounds__(256) void k_from_f32(const float* __restrict__ in, T* __restrict__ out, int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) Store<T>::st(out + i, in[i]);
+}
+
+void qr_combine(const float* y, const float* y2, float alpha, float beta, float ident, int d, float* out, float* out_t, hipStream_t s) {
+  hipLaunchKernelGGL(k_qr_combine, dim3(d / 32, d / 32), dim3(256), 0, s, y, y2, alpha, beta, ident, d, out, out_t);
+}
+
+// workspace of the QR calls: binary32 d x d matrices
+struct QrSlots {
+  float* base; int64_t dd; int J;
+  float* x() const { return base; }                                  // S / 2^J
+  float* h(int k) const { return base + (int64_t)(k - 1) * dd; }     // H_k, k = 2 .. kQrOrder  (slots 1 .. kQrOrder-1)
+  float* q(int i) const { return base + (int64_t)(kQrOrder + i) * dd; }              // Q_i, i = 0 .. J
+  float* qt(int i) const { return base + (int64_t)(kQrOrder + J + 1 + i) * dd; }     // Q_i^T
+  float* tmp(int t) const { return base + (int64_t)(kQrOrder + 2 * (J + 1) + t) * dd; }   // six temporaries
+  static int64_t count(int J) { return kQrOrder + 2 * (J + 1) + 6; }
+};
+
+int check_qr_args(const char* who, int64_t d, int dtype, int squarings) {
+  if (dtype != AE_F32 && dtype != AE_BF16) return fail(AE_EINVAL, "%s: bad dtype", who);
+  if (d < 32 || d % 32 != 0 || d > 16384) return fail(AE_EINVAL, "%s: d must be a multiple of 32 between 32 and 16384", who);
+  if (squarings < 0 || squarings > 16) return fail(AE_EINVAL, "%s: squarings must be 0 .. 16", who);
+  return AE_OK;
+}
+
 int check_lu_size(const char* who, int64_t d, int dtype) {
   if (dtype != AE_F32 && dtype != AE_BF16) return fail(AE_EINVAL, "%s: bad dtype", who);
   if (d < 32 || d % 32 != 0 || d > 16384) return fail(AE_EINVAL, "%s: d must be a multiple of 32 between 32 and 16384", who);
@@ -477,6 +559,102 @@ extern "C" int model_lu_backward(const void* g, const float* lp, const float* up
     hipLaunchKernelGGL((k_lu_grad_lower<float>), dim3(grid), dim3(256), 0, s, (const float*)dl, (int)d, d_lp);
   }
   return launch_status("lu_backward");
+}
+
+extern "C" int model_qr_workspace(int64_t d, int squarings, int64_t* bytes) {
+  using namespace ae;
+  if (!bytes) return fail(AE_EINVAL, "model_qr_workspace: null argument");
+  AE_TRY(check_qr_args("model_qr_workspace", d, AE_F32, squarings));
+  *bytes = QrSlots::count(squarings) * d * d * 4 + 1024;
+  return AE_OK;
+}
+
+extern "C" int model_qr_compose(const float* g, const float* rp, const float* log_s, const float* sign_s, int64_t d, int dtype,
+                                int squarings, void* a_out, void* workspace, void* stream) {
+  using namespace ae;
+  if (!g || !rp || !log_s || !sign_s || !a_out || !workspace) return fail(AE_EINVAL, "model_qr_compose: null argument");
+  AE_TRY(check_qr_args("model_qr_compose", d, dtype, squarings));
+  if (((reinterpret_cast<uintptr_t>(workspace) | reinterpret_cast<uintptr_t>(a_out) | reinterpret_cast<uintptr_t>(rp)) & 15) != 0)
+    return fail(AE_EINVAL, "model_qr_compose: the matrices and the workspace must be 16-byte aligned");
+  hipStream_t s = (hipStream_t)stream;
+  const int n = (int)d, J = squarings;
+  const QrSlots w{reinterpret_cast<float*>(workspace), d * d, J};
+  const dim3 tgrid(n / 32, n / 32);
+  hipLaunchKernelGGL(k_qr_skew, tgrid, dim3(256), 0, s, g, 0.5f / (float)(1 << J), n, w.x());
+  float* ht = w.tmp(0);
+  float* y = w.tmp(1);
+  qr_combine(w.x(), nullptr, 1.0f / kQrOrder, 0.0f, 1.0f, n, w.h(kQrOrder), ht, s);        // H_M = I + X / M
+  AE_TRY(launch_status("qr_first"));
+  for (int k = kQrOrder - 1; k >= 1; --k) {
+    AE_TRY(dense_product(w.x(), ht, y, n, AE_F32, CONV_TRI_NONE, s));                       // X H_{k+1}
+    float* hk = k >= 2 ? w.h(k) : w.q(0);
+    float* hkt = k >= 2 ? ht : w.qt(0);
+    qr_combine(y, nullptr, 1.0f / (float)k, 0.0f, 1.0f, n, hk, hkt, s);                     // H_k = I + X H_{k+1} / k
+    AE_TRY(launch_status("qr_horner"));
+  }
+  for (int i = 0; i < J; ++i) {
+    AE_TRY(dense_product(w.q(i), w.qt(i), w.q(i + 1), n, AE_F32, CONV_TRI_NONE, s));        // Q_{i+1} = Q_i Q_i
+    qr_combine(w.q(i + 1), nullptr, 1.0f, 0.0f, 0.0f, n, nullptr, w.qt(i + 1), s);
+    AE_TRY(launch_status("qr_square"));
+  }
+  float* rdt = w.tmp(2);                                                                     // (R + diag s)^T
+  LuSrc q{nullptr, rp, log_s, sign_s, nullptr, nullptr, n};
+  launch_build_transposed<float, LU_UD>(q, rdt, s);
+  AE_TRY(launch_status("qr_build"));
+  if (dtype == AE_F32) return dense_product(w.q(J), rdt, a_out, n, AE_F32, CONV_TRI_NONE, s);
+  AE_TRY(dense_product(w.q(J), rdt, y, n, AE_F32, CONV_TRI_NONE, s));
+  hipLaunchKernelGGL((k_from_f32<bf16_t>), dim3(lu_grid(d * d)), dim3(256), 0, s, (const float*)y, (bf16_t*)a_out, d * d);
+  return launch_status("qr_compose");
+}
+
+extern "C" int model_qr_backward(const void* g_a, const float* rp, const float* log_s, const float* sign_s, int64_t d, int dtype,
+                                 int squarings, float* d_g, float* d_rp, float* d_log_s, void* workspace, void* stream) {
+  using namespace ae;
+  if (!g_a || !rp || !log_s || !sign_s || !d_g || !d_rp || !d_log_s || !workspace) return fail(AE_EINVAL, "model_qr_backward: null argument");
+  AE_TRY(check_qr_args("model_qr_backward", d, dtype, squarings));
+  if (((reinterpret_cast<uintptr_t>(workspace) | reinterpret_cast<uintptr_t>(g_a) | reinterpret_cast<uintptr_t>(rp) |
+        reinterpret_cast<uintptr_t>(d_rp)) & 15) != 0)
+    return fail(AE_EINVAL, "model_qr_backward: the matrices and the workspace must be 16-byte aligned");
+  hipStream_t s = (hipStream_t)stream;
+  const int n = (int)d, J = squarings;
+  const int64_t dd = d * d;
+  const QrSlots w{reinterpret_cast<float*>(workspace), dd, J};
+  float *t0 = w.tmp(0), *t1 = w.tmp(1), *t2 = w.tmp(2), *t3 = w.tmp(3), *t4 = w.tmp(4), *t5 = w.tmp(5);
+  // dA in binary32 (t0) and its transpose (t1)
+  if (dtype == AE_BF16) hipLaunchKernelGGL((k_to_f32<bf16_t>), dim3(lu_grid(dd)), dim3(256), 0, s, (const bf16_t*)g_a, t0, dd);
+  else hipLaunchKernelGGL((k_to_f32<float>), dim3(lu_grid(dd)), dim3(256), 0, s, (const float*)g_a, t0, dd);
+  qr_combine(t0, nullptr, 1.0f, 0.0f, 0.0f, n, nullptr, t1, s);
+  AE_TRY(launch_status("qr_backward_in"));
+  // d(R + diag s) = Q^T dA: strictly upper part and diagonal
+  AE_TRY(dense_product(w.qt(J), t1, t2, n, AE_F32, CONV_TRI_NONE, s));
+  hipLaunchKernelGGL((k_lu_grad_upper<float>), dim3(lu_grid(dd / 8 * 4)), dim3(256), 0, s, (const float*)t2, log_s, sign_s, n, d_rp, d_log_s);
+  // dQ_J = dA (R + diag s)^T  -> cur (t3), cur^T (t4)
+  LuSrc q{nullptr, rp, log_s, sign_s, nullptr, nullptr, n};
+  launch_build_rows<float, LU_UD>(q, t2, s);
+  AE_TRY(launch_status("qr_build"));
+  AE_TRY(dense_product(t0, t2, t3, n, AE_F32, CONV_TRI_NONE, s));
+  qr_combine(t3, nullptr, 1.0f, 0.0f, 0.0f, n, nullptr, t4, s);
+  float *cur = t3, *cur_t = t4;
+  // squarings in reverse: dQ_i = dQ_{i+1} Q_i^T + Q_i^T dQ_{i+1}
+  for (int i = J - 1; i >= 0; --i) {
+    AE_TRY(dense_product(cur, w.q(i), t0, n, AE_F32, CONV_TRI_NONE, s));
+    AE_TRY(dense_product(w.qt(i), cur_t, t1, n, AE_F32, CONV_TRI_NONE, s));
+    qr_combine(t0, t1, 1.0f, 1.0f, 0.0f, n, cur, cur_t, s);
+    AE_TRY(launch_status("qr_backward_square"));
+  }
+  // Horner steps in reverse: cur = dH_k;  dX += dH_k H_{k+1}^T / k,  dH_{k+1} = X^T dH_k / k = -X dH_k / k
+  float* dx = t5;
+  for (int k = 1; k <= kQrOrder - 1; ++k) {
+    AE_TRY(dense_product(cur, w.h(k + 1), t0, n, AE_F32, CONV_TRI_NONE, s));
+    hipLaunchKernelGGL(k_qr_axpy, dim3(lu_grid(dd)), dim3(256), 0, s, dx, (const float*)t0, 1.0f / (float)k, k == 1 ? 1 : 0, dd);
+    AE_TRY(dense_product(w.x(), cur_t, t1, n, AE_F32, CONV_TRI_NONE, s));
+    qr_combine(t1, nullptr, -1.0f / (float)k, 0.0f, 0.0f, n, cur, cur_t, s);
+    AE_TRY(launch_status("qr_backward_horner"));
+  }
+  hipLaunchKernelGGL(k_qr_axpy, dim3(lu_grid(dd)), dim3(256), 0, s, dx, (const float*)cur, 1.0f / kQrOrder, 0, dd);   // H_M = I + X / M
+  // X = (G - G^T) / (2 * 2^J):  dG = (dX - dX^T) / (2 * 2^J)
+  hipLaunchKernelGGL(k_qr_skew, dim3(n / 32, n / 32), dim3(256), 0, s, (const float*)dx, 0.5f / (float)(1 << J), n, d_g);
+  return launch_status("qr_backward");
 }
 
 extern "C" int model_lu_inverse_workspace(int64_t d, int64_t* bytes) {

@@ -47,7 +47,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   for (int r = 0; r < 8; ++r)
 #pragma unroll
     for (int c = 0; c < 4; ++c) f[r][c] = random_data ? calib_random_pair(h) : 0x3f803f80u;
-  unsigned base = (unsigned)(size_t)(calib_lds_char*)smem + (unsigned)((tid >> 6) * 8192 + lane * 16);
+  [[maybe_unused]] unsigned base = (unsigned)(size_t)(calib_lds_char*)smem + (unsigned)((tid >> 6) * 8192 + lane * 16);
   for (int it = 0; it < iters; ++it) {
 #if defined(__HIP_DEVICE_COMPILE__)
 #pragma unroll

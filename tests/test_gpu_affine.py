@@ -221,3 +221,69 @@ def test_inverse_argument_checks(ae):
     assert ae.lib.model_lu_inverse(p, p, p, p, p, 384, 0, p, p, None) == -1
     assert ae.lib.model_lu_inverse(p, p, p, p, p, 128, 3, p, p, None) == -1
     assert ae.lib.model_lu_inverse(None, p, p, p, p, 128, 0, p, p, None) == -1
+
+
+# ------------------------------------------------------------------ QR parametrisation (Eq. 5)
+def _qr_run(ae, params, d, dtype, g_a=None, squarings=5):
+    import torch
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    dp = [torch.from_numpy(a).cuda() for a in params]
+    a = torch.full((d, d), float("nan"), dtype=td, device="cuda")
+    ws = torch.empty(ae.model_qr_workspace(d, squarings), dtype=torch.uint8, device="cuda")
+    ae.model_qr_compose(*dp, d, a, ws, squarings)
+    out = [a.float().cpu().numpy().astype(np.float64)]
+    if g_a is not None:
+        gt = torch.from_numpy(g_a.astype(np.float32)).cuda().to(td).contiguous()
+        dg = torch.full((d, d), float("nan"), device="cuda")
+        dr = torch.full((d, d), float("nan"), device="cuda")
+        dls = torch.full((d,), float("nan"), device="cuda")
+        ae.model_qr_backward(gt, dp[1], dp[2], dp[3], d, dg, dr, dls, ws, squarings)
+        out += [t.cpu().numpy().astype(np.float64) for t in (dg, dr, dls)]
+    torch.cuda.synchronize()
+    return out
+
+
+QR_CASES = [(32, "random"), (96, "random"), (256, "bd_orthogonal"), (512, "random")]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("d,kind", QR_CASES)
+def test_qr_compose_and_backward_match_oracle(ae, d, kind, dtype):
+    """The exponential runs in binary32 whatever the storage type; bf16 only rounds dA on the way in and A on the way out."""
+    params = wl.make_qr_params(d, seed=d + 3, kind=kind, noise=1e-3 if kind == "bd_orthogonal" else 0.0)
+    if kind == "random":
+        params = (params[0] * 2.0,) + tuple(params[1:])      # a rotation well away from the identity
+    g_a = _round(np.random.default_rng(d).standard_normal((d, d)), dtype).astype(np.float64)
+    a, dg, dr, dls = _qr_run(ae, params, d, dtype, g_a)
+    ref = ao.qr_compose(*params)
+    assert _close(a, ref, TOL[dtype]), np.abs(a - ref).max()
+    r_g, r_r, r_ls = ao.qr_gradients(g_a, *params)
+    tol = TOL["f32"]                                          # the gradients come out in binary32 in both cases
+    assert _close(dg, r_g, tol), np.abs(dg - r_g).max()
+    assert _close(dr, r_r, tol) and _close(dls, r_ls, tol)
+    assert np.array_equal(dg, -dg.T) and np.array_equal(np.tril(dr), np.zeros((d, d)))
+    if kind == "bd_orthogonal" and dtype == "f32":
+        assert np.abs(a @ a.T - np.eye(d)).max() < 0.02      # the initialisation: orthogonal up to the noise
+
+
+def test_qr_more_squarings_for_a_large_generator(ae):
+    """||S|| around 40: five squarings leave X too large for the polynomial, eight are enough."""
+    d = 64
+    params = wl.make_qr_params(d, seed=9)
+    params = (params[0] * 40.0,) + tuple(params[1:])
+    ref = ao.qr_compose(*params)
+    a8, = _qr_run(ae, params, d, "f32", squarings=8)
+    assert _close(a8, ref, 1e-3), np.abs(a8 - ref).max()
+
+
+def test_qr_argument_checks(ae):
+    import torch
+    t = torch.zeros(64 * 64, device="cuda")
+    p = C.c_void_p(t.data_ptr())
+    n = C.c_int64()
+    assert ae.lib.model_qr_workspace(48, 5, C.byref(n)) == -1
+    assert ae.lib.model_qr_workspace(64, 17, C.byref(n)) == -1
+    assert ae.lib.model_qr_workspace(64, 5, C.byref(n)) == 0 and n.value == 28 * 64 * 64 * 4 + 1024
+    assert ae.lib.model_qr_compose(p, p, p, p, 64, 0, -1, p, p, None) == -1
+    assert ae.lib.model_qr_compose(None, p, p, p, 64, 0, 5, p, p, None) == -1
+    assert ae.lib.model_qr_backward(p, p, p, p, 64, 9, 5, p, p, p, p, None) == -1
