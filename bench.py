@@ -435,6 +435,77 @@ def bench_fold(torch, ae, args):
     }
 
 
+# measured HBM bytes per product launch of the QR parametrisation (profiles/qr_param.md)
+QR_TRAFFIC_BYTES = {"f32": 8.44e8}
+
+
+def bench_qr_param(torch, ae, args):
+    """One step = the QR parametrisation A = exp((G - G^T)/2)(R + diag s) of Eq. (5) for one d x d matrix, d = 4 096:
+    compose A (order-10 Taylor polynomial, five squarings), the volume regulariser, and the parameter gradients from
+    dLoss/dA through the stored chain: 15 + 30 dense binary32 products of 2 d^3 FLOPs each."""
+    d, squarings = 4096, 5
+    td = torch.bfloat16 if args.dtype == "bf16" else torch.float32
+    params = wl.make_qr_params(d, seed=13, kind="bd_orthogonal", noise=1e-3)
+    g, rp, ls, sg = [torch.from_numpy(a).cuda() for a in params]
+    ga_h = np.random.default_rng(14).standard_normal((d, d)).astype(np.float32)
+    ga = torch.from_numpy(ga_h).cuda().to(td).contiguous()
+    a = torch.empty((d, d), dtype=td, device="cuda")
+    dg, dr = torch.empty((d, d), device="cuda"), torch.empty((d, d), device="cuda")
+    dls, vgrad, val = torch.empty(d, device="cuda"), torch.empty(d, device="cuda"), torch.empty(1, device="cuda")
+    ws = torch.empty(ae.model_qr_workspace(d, squarings), dtype=torch.uint8, device="cuda")
+
+    def step():
+        ae.model_qr_compose(g, rp, ls, sg, d, a, ws, squarings)
+        ae.model_vol_penalty(ls, d, val, vgrad)
+        ae.model_qr_backward(ga, rp, ls, sg, d, dg, dr, dls, ws, squarings)
+
+    steps, warmup = min(args.steps, 5), min(args.warmup, 2)
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ae.model_lu_timing(True)                 # HIP events around every matrix-core product inside the library
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    gemm_ms, launches = ae.model_lu_timing(False)
+    avg_ms = gemm_ms / max(launches, 1)
+    per_step = launches // steps
+    flops_per_launch = 2.0 * d ** 3
+    ach = flops_per_launch / avg_ms / 1e9
+    from oracle import affine_oracle as ao
+    cpu = None
+    if not args.no_cpu_baseline:
+        c0 = time.perf_counter()
+        ao.qr_compose(*params)
+        ao.vol_penalty(params[2])
+        ao.qr_gradients(ga_h.astype(np.float64), *params)
+        ct = time.perf_counter() - c0
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = 1
+        cpu = {"value": 1.0 / ct, "unit": "matrices/s", "cores": cores, "kind": "oracle",
+               "sample": "one full step (d = 4096, float64, library expm and its Frechet derivative) in %.1f s" % ct}
+    return {
+        "metric": "matrices/sec, QR-parametrised 4096 x 4096 matrix: compose + regulariser + parameter gradients",
+        "value": steps / dt, "unit": "matrices/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": dt / steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "qr_param: A = exp((G - G^T)/2)(R + diag s), d = 4096, block-orthogonal initialisation + noise",
+                   "d": d, "squarings": squarings, "taylor_order": 10, "storage_of_A_and_dA": args.dtype},
+        "roofline": {"bound": "mfma", "kernel": "k_igemm<float> (dense)", "achieved": ach, "peak": PEAK["f32"], "unit": "TFLOP/s",
+                     "frac": ach / PEAK["f32"], "traffic": QR_TRAFFIC_BYTES.get("f32"), "avg_ms": avg_ms,
+                     "launches_per_step": per_step, "flops_per_launch": flops_per_launch, "bytes_per_launch": 3.0 * d * d * 4},
+        "cpu_baseline": cpu,
+    }
+
+
 def cpu_baseline(name, budget_s=20.0):
     """The oracle as it stands, on a bounded sample of the same workload (same layer list and
     resolution, smaller batch), timed on this machine's host cores."""
@@ -490,6 +561,9 @@ def main():
     ap.add_argument("--lu-param", action="store_true",
                     help="benchmark the LU parametrisation of Eq. (4) (compose, regulariser, parameter gradients; d = 4096) "
                          "instead of a network: one JSON line with roofline and cpu_baseline")
+    ap.add_argument("--qr-param", action="store_true",
+                    help="benchmark the QR parametrisation of Eq. (5) (matrix exponential by scaling and squaring, d = 4096; "
+                         "at most 5 timed steps) instead of a network: one JSON line with roofline and cpu_baseline")
     ap.add_argument("--fold", action="store_true",
                     help="benchmark the folding of two affine transformations into the four projections of one attention block "
                          "(d = 4096) instead of a network: one JSON line with roofline and cpu_baseline")
@@ -526,6 +600,9 @@ def main():
         return
     if args.fold:
         print(json.dumps(bench_fold(torch, ae, args)))
+        return
+    if args.qr_param:
+        print(json.dumps(bench_qr_param(torch, ae, args)))
         return
     if args.calibrate_mfma:
         res = {"kernel": "k_calib_mfma", "nominal_peak_tflops": PEAK["bf16"]}

@@ -266,6 +266,22 @@ def test_qr_compose_and_backward_match_oracle(ae, d, kind, dtype):
         assert np.abs(a @ a.T - np.eye(d)).max() < 0.02      # the initialisation: orthogonal up to the noise
 
 
+def test_qr_full_size(ae):
+    """d = 4 096, the size bench.py times (bf16 storage of A and dA): A in full against the oracle; the gradients of
+    the launch configuration at d = 1 024, where the oracle's Frechet derivative takes seconds."""
+    d = 4096
+    params = wl.make_qr_params(d, seed=13, kind="bd_orthogonal", noise=1e-3)
+    a, = _qr_run(ae, params, d, "bf16")
+    assert _close(a, ao.qr_compose(*params), TOL["bf16"])
+    d = 1024
+    params = wl.make_qr_params(d, seed=14, kind="bd_orthogonal", noise=1e-3)
+    g_a = _round(np.random.default_rng(1).standard_normal((d, d)), "bf16").astype(np.float64)
+    a, dg, dr, dls = _qr_run(ae, params, d, "bf16", g_a)
+    r_g, r_r, r_ls = ao.qr_gradients(g_a, *params)
+    assert _close(a, ao.qr_compose(*params), TOL["bf16"])
+    assert _close(dg, r_g, TOL["f32"]) and _close(dr, r_r, TOL["f32"]) and _close(dls, r_ls, TOL["f32"])
+
+
 def test_qr_more_squarings_for_a_large_generator(ae):
     """||S|| around 40: five squarings leave X too large for the polynomial, eight are enough."""
     d = 64
