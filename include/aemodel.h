@@ -254,12 +254,17 @@ int model_lu_timing(int enable, double* gemm_ms, int64_t* launches);
  * model_qr_compose   writes a_out = A [d][d] in dtype and leaves the intermediate matrices in the workspace.
  * model_qr_backward  given g_a = dLoss/dA [d][d] in dtype and THE SAME workspace, untouched since model_qr_compose
  *   ran on the same parameters, writes d_g [d][d] (skew-symmetric), d_rp [d][d] (strictly upper part, zero
- *   elsewhere) and d_log_s [d] in binary32. */
+ *   elsewhere) and d_log_s [d] in binary32.
+ * model_qr_inverse   A^-1 = (R + diag s)^-1 Q^T into a_inv_out [d][d] in dtype: Q is read from qr_workspace (the
+ *   workspace model_qr_compose left, same parameters and squarings), the triangular factor is inverted as in
+ *   model_lu_inverse; d: 128 times a power of two; workspace: model_lu_inverse_workspace(d) bytes. */
 int model_qr_workspace(int64_t d, int squarings, int64_t* bytes);
 int model_qr_compose(const float* g, const float* rp, const float* log_s, const float* sign_s, int64_t d, int dtype,
                      int squarings, void* a_out, void* workspace, void* stream);
 int model_qr_backward(const void* g_a, const float* rp, const float* log_s, const float* sign_s, int64_t d, int dtype,
                       int squarings, float* d_g, float* d_rp, float* d_log_s, void* workspace, void* stream);
+int model_qr_inverse(const float* rp, const float* log_s, const float* sign_s, int64_t d, int dtype, int squarings,
+                     const void* qr_workspace, void* a_inv_out, void* workspace, void* stream);
 
 /* Folding of affine transformations T(x) = A x + v into a linear layer f(x) = W x + b (the paper's appendix
  * "Folding & Transformation Structure"): the layer x -> T_l(f(T_r^-1(x))) has

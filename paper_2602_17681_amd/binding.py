@@ -23,7 +23,7 @@ SYMBOLS = [
     "model_set_sample_offset", "model_forward", "model_backward", "model_loss_mse", "model_noise",
     "model_pnorm_awgn", "model_gen_bits", "model_count_errors", "model_num_steps", "model_step_info",
     "model_get_activation", "model_timing_enable", "model_set_overlap", "model_calibrate_mfma", "model_mx_quantize", "model_transform_mse_workspace",
-    "model_transform_mse", "model_lu_workspace", "model_lu_compose", "model_lu_backward", "model_vol_penalty", "model_lu_inverse_workspace", "model_lu_inverse", "model_lu_timing", "model_qr_workspace", "model_qr_compose", "model_qr_backward", "model_fold_workspace", "model_fold_linear", "model_fold_embedding", "model_timing_slots",
+    "model_transform_mse", "model_lu_workspace", "model_lu_compose", "model_lu_backward", "model_vol_penalty", "model_lu_inverse_workspace", "model_lu_inverse", "model_lu_timing", "model_qr_workspace", "model_qr_compose", "model_qr_backward", "model_qr_inverse", "model_fold_workspace", "model_fold_linear", "model_fold_embedding", "model_timing_slots",
     "model_timing_read", "model_timing_reset", "model_last_error",
 ]
 
@@ -73,6 +73,7 @@ def _load():
     L.model_qr_workspace.argtypes = [C.c_int64, C.c_int, i64p]
     L.model_qr_compose.argtypes = [vp, vp, vp, vp, C.c_int64, C.c_int, C.c_int, vp, vp, vp]
     L.model_qr_backward.argtypes = [vp, vp, vp, vp, C.c_int64, C.c_int, C.c_int, vp, vp, vp, vp, vp]
+    L.model_qr_inverse.argtypes = [vp, vp, vp, C.c_int64, C.c_int, C.c_int, vp, vp, vp, vp]
     L.model_fold_workspace.argtypes = [C.c_int64, C.c_int64, C.c_int64, C.c_int64, C.c_int, i64p]
     L.model_fold_linear.argtypes = [vp, vp, C.c_int64, C.c_int64, vp, C.c_int64, vp, vp, C.c_int64, vp, C.c_int, vp, vp, vp, vp]
     L.model_fold_embedding.argtypes = [vp, C.c_int64, C.c_int64, vp, vp, C.c_int, vp, vp]
@@ -322,6 +323,15 @@ def model_qr_backward(g_a, rp, log_s, sign_s, d, d_g, d_rp, d_log_s, workspace, 
     _check(lib.model_qr_backward(_ptr(g_a), _ptr(rp, torch.float32), _ptr(log_s, torch.float32), _ptr(sign_s, torch.float32), d, dtype,
                                  squarings, _ptr(d_g, torch.float32), _ptr(d_rp, torch.float32), _ptr(d_log_s, torch.float32),
                                  _ptr(workspace), _stream()))
+
+
+def model_qr_inverse(rp, log_s, sign_s, d, qr_workspace, a_inv_out, workspace, squarings=5):
+    dtype = AE_BF16 if a_inv_out.dtype == torch.bfloat16 else AE_F32
+    assert rp.numel() == d * d and a_inv_out.numel() == d * d
+    assert qr_workspace.numel() * qr_workspace.element_size() >= model_qr_workspace(d, squarings)
+    assert workspace.numel() * workspace.element_size() >= model_lu_inverse_workspace(d)
+    _check(lib.model_qr_inverse(_ptr(rp, torch.float32), _ptr(log_s, torch.float32), _ptr(sign_s, torch.float32), d, dtype, squarings,
+                                _ptr(qr_workspace), _ptr(a_inv_out), _ptr(workspace), _stream()))
 
 
 def model_fold_workspace(out, in_, p, q, dtype):

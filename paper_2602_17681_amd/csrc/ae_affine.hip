@@ -657,6 +657,29 @@ extern "C" int model_qr_backward(const void* g_a, const float* rp, const float* 
   return launch_status("qr_backward");
 }
 
+extern "C" int model_qr_inverse(const float* rp, const float* log_s, const float* sign_s, int64_t d, int dtype, int squarings,
+                                const void* qr_workspace, void* a_inv_out, void* workspace, void* stream) {
+  using namespace ae;
+  if (!rp || !log_s || !sign_s || !qr_workspace || !a_inv_out || !workspace) return fail(AE_EINVAL, "model_qr_inverse: null argument");
+  AE_TRY(check_qr_args("model_qr_inverse", d, dtype, squarings));
+  if (d < 128 || d % 128 != 0 || ((d / 128) & (d / 128 - 1)) != 0)
+    return fail(AE_EINVAL, "model_qr_inverse: d must be 128 times a power of two, at most 16384");
+  if (((reinterpret_cast<uintptr_t>(workspace) | reinterpret_cast<uintptr_t>(qr_workspace) | reinterpret_cast<uintptr_t>(a_inv_out)) & 15) != 0)
+    return fail(AE_EINVAL, "model_qr_inverse: the matrices and the workspaces must be 16-byte aligned");
+  hipStream_t s = (hipStream_t)stream;
+  const int64_t dd = d * d;
+  const QrSlots w{const_cast<float*>(reinterpret_cast<const float*>(qr_workspace)), dd, squarings};
+  float* f = reinterpret_cast<float*>(workspace);
+  float *mneg = f, *tt = f + dd, *rdinv_t = f + 2 * dd, *rdinv = f + 3 * dd, *z = f + 4 * dd;
+  LuSrc q{nullptr, rp, log_s, sign_s, nullptr, nullptr, (int)d};
+  AE_TRY(tri_inverse<1>(q, mneg, tt, rdinv_t, rdinv, s));                 // ((R + diag s)^T)^-1 and its transpose (R + diag s)^-1
+  // A^-1 = (R + diag s)^-1 Q^T = x w^T with w = Q
+  if (dtype == AE_F32) return dense_product(rdinv, w.q(squarings), a_inv_out, (int)d, AE_F32, CONV_TRI_NONE, s);
+  AE_TRY(dense_product(rdinv, w.q(squarings), z, (int)d, AE_F32, CONV_TRI_NONE, s));
+  hipLaunchKernelGGL((k_from_f32<bf16_t>), dim3(lu_grid(dd)), dim3(256), 0, s, (const float*)z, (bf16_t*)a_inv_out, dd);
+  return launch_status("qr_inverse");
+}
+
 extern "C" int model_lu_inverse_workspace(int64_t d, int64_t* bytes) {
   using namespace ae;
   if (!bytes) return fail(AE_EINVAL, "model_lu_inverse_workspace: null argument");

@@ -282,6 +282,27 @@ def test_qr_full_size(ae):
     assert _close(dg, r_g, TOL["f32"]) and _close(dr, r_r, TOL["f32"]) and _close(dls, r_ls, TOL["f32"])
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_qr_inverse_matches_the_inverse_of_the_composed_matrix(ae, dtype):
+    import torch
+    d = 512
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    params = wl.make_qr_params(d, seed=31)
+    params = (params[0] * 2.0,) + tuple(params[1:])
+    dp = [torch.from_numpy(a).cuda() for a in params]
+    a = torch.empty((d, d), dtype=td, device="cuda")
+    ws = torch.empty(ae.model_qr_workspace(d, 5), dtype=torch.uint8, device="cuda")
+    ae.model_qr_compose(*dp, d, a, ws, 5)
+    ainv = torch.full((d, d), float("nan"), dtype=td, device="cuda")
+    ws2 = torch.empty(ae.model_lu_inverse_workspace(d), dtype=torch.uint8, device="cuda")
+    ae.model_qr_inverse(dp[1], dp[2], dp[3], d, ws, ainv, ws2, 5)
+    ref = np.linalg.inv(ao.qr_compose(*params))
+    assert _close(ainv.float().cpu().numpy().astype(np.float64), ref, TOL[dtype])
+    assert ae.lib.model_qr_inverse(None, None, None, 512, 0, 5, None, None, None, None) == -1
+    p = C.c_void_p(ws.data_ptr())
+    assert ae.lib.model_qr_inverse(p, p, p, 384, 0, 5, p, p, p, None) == -1       # 3 blocks: not a power of two
+
+
 def test_qr_more_squarings_for_a_large_generator(ae):
     """||S|| around 40: five squarings leave X too large for the polynomial, eight are enough."""
     d = 64
