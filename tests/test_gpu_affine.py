@@ -185,6 +185,22 @@ def test_inverse_full_size(ae):
     assert np.abs(a @ got32 - np.eye(d)).max() < 1e-4
 
 
+def test_largest_size_exercised(ae):
+    """d = 8 192 (the widest residual stream of the model family the paper evaluates): A in full against the oracle, and
+    the inverse through the residual A A^-1 = I on sampled columns."""
+    d = 8192
+    params = wl.make_lu_params(d, seed=17, kind="bd_hadamard", noise=5e-4)
+    a_ref = ao.lu_compose(*params)
+    a = _compose(ae, params, d, "bf16")
+    assert _close(a, a_ref, TOL["bf16"])
+    del a
+    inv = _inverse(ae, params, d, "f32")
+    cols = np.arange(0, d, 127)
+    resid = a_ref @ inv[:, cols]
+    resid[cols, np.arange(len(cols))] -= 1.0
+    assert np.abs(resid).max() < 1e-4
+
+
 def test_inverse_feeds_the_transformation_error(ae):
     """The whole chain on the GPU: parameters -> A and A^-1 -> E(T), against the oracle chain with numpy's inverse."""
     import torch
