@@ -199,7 +199,7 @@ int model_mx_quantize(const void* x, void* q, int64_t rows, int64_t d, int block
  * a_mat = A and a_inv = A^-1 are [d][d] row-major in the tensor's dtype (the caller supplies the inverse),
  * v and inv_shift = -A^-1 v are binary32 [d].  Both products run on the matrix cores with binary32
  * accumulation; the quantiser and the squared-error sums are epilogues of the two GEMMs.
- * workspace: model_transform_mse_workspace bytes of device memory.  block must be 32, d a multiple of
+ * workspace: model_transform_mse_workspace bytes of device memory.  block: a power of two, 8 (bf16) / 4 (fp32) to 64; d a multiple of
  * 128, rows a multiple of 256 (bf16) or 128 (fp32), every tensor below 2 GiB: AE_EINVAL otherwise. */
 int model_transform_mse_workspace(int64_t rows, int64_t d, int dtype, int64_t* bytes);
 int model_transform_mse(const void* x, const void* a_mat, const float* v, const void* a_inv, const float* inv_shift,

@@ -52,10 +52,12 @@ struct IgemmParams {
   // w + phase*N*K); row (n, i, j) of phase (a, b) is output pixel (2i+a, 2j+b) of a 2Hc x 2Wc image
   int phases;
   // epilogue variants of the dense-GEMM use (EPI template parameter of k_igemm):
-  //   1: the stored output is MX block-quantised (blocks of 32 output columns, FP4 E2M1 elements);
+  //   1: the stored output is MX block-quantised (blocks of mx_block output columns: a power of two from one 16-byte
+  //      chunk up to the 64 columns of a wave tile; FP4 E2M1 elements);
   //   2: nothing is stored; the epilogue forms resid[m][n] - (acc + bias) and leaves per-tile column sums of it
   //      and of its square in `partial` (resid: [M][N] in the storage type)
   const void* resid;
+  int mx_block;
   // Square dense products (M = N = K) with triangular operands: K range per tile, and tiles nobody wants skipped.
   //   1: x[m][k] = 0 for k > m and w[n][k] = 0 for k > n (lower times upper): K ends at min(last row, last column) + 1
   //   2: x[m][k] = 0 for k < m, wanted outputs n >= m: K starts at the tile's first row; tiles below the diagonal return
@@ -153,14 +155,14 @@ __device__ __forceinline__ void igemm_store_interior(const floatx16 (&acc)[MI][N
       T* dst = p.phases == 1 ? yrow + (int64_t)(i * 32 + lr) * N + ch * EPC
                              : ycol + igemm_out_row(p, mrow0 + i * 32 + lr, phase) * N + ch * EPC;
       if constexpr (MXQ) {
-        // MX block quantisation of the stored row: a block of 32 columns is 32/EPC neighbouring lanes of this pass
+        // MX block quantisation of the stored row: a block of mx_block columns is mx_block/EPC neighbouring lanes of this
+        // pass (a staged row is CPRO >= mx_block/EPC consecutive lanes, blocks do not straddle rows)
         float f[EPC];
         Store<T>::ldv(&stage[lr * SW + ch * EPC], f);
         float amax = 0.0f;
 #pragma unroll
         for (int t = 0; t < EPC; ++t) amax = fmaxf(amax, fabsf(f[t]));
-#pragma unroll
-        for (int off = 1; off < 32 / EPC; off <<= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
+        for (int off = 1; off < p.mx_block / EPC; off <<= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
         if (amax > 0.0f) {
           const int k = mx_scale_exp(amax);
           const float sc = ldexpf(1.0f, k), inv_sc = ldexpf(1.0f, -k);
@@ -963,6 +965,10 @@ bool conv_epi_usable(const ConvArgs& a) {
   if (a.y_aux || a.act != ACT_NONE || a.cout % 128 != 0) return false;
   if (a.epi == CONV_EPI_RESID && (!a.partial || !a.resid)) return false;
   if (a.epi == CONV_EPI_MXQ && a.partial) return false;
+  if (a.epi == CONV_EPI_MXQ) {
+    const int epc = 16 / (int)dtype_size(a.dtype);
+    if (a.mx_block < epc || a.mx_block > 64 || (a.mx_block & (a.mx_block - 1)) != 0) return false;
+  }
   const IgemmTile t = pick_tile(a.n, a.cout, a.cin, (int)dtype_size(a.dtype));
   return (t.bn == 128 || t.bn == 256) && a.n % t.bm == 0;
 }
@@ -987,6 +993,7 @@ int launch_conv_mfma(const ConvArgs& a0, hipStream_t s) {
   p.Hc = a.hc; p.Wc = a.wc; p.Cin = a.cin; p.ksz = a.k; p.up = a.up; p.act = a.act;
   p.Hv = a.hc; p.Wv = a.wc; p.stride = 1; p.pad = (a.k - 1) >> 1; p.phases = 1;
   p.resid = a0.resid;
+  p.mx_block = a0.mx_block;
   p.tri = a0.tri;
   p.tri_b = a0.tri_b;
   if (a0.tri >= 8 && (a0.tri > 10 || a.dtype != AE_F32 || a0.tri_b < 128 || a0.tri_b % 128 != 0 || a.n % (2 * a0.tri_b) != 0))

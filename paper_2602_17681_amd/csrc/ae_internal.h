@@ -140,11 +140,13 @@ struct ConvArgs {
   //                   which also replaces the 2x2 sum over each upsampled pixel.
   int geom = 0;
   // Dense-GEMM epilogues (k = 1 layers whose tiles all lie inside the output, no split-K):
-  //   CONV_EPI_MXQ    the stored output is MX block-quantised (blocks of 32 columns, FP4 E2M1 elements);
+  //   CONV_EPI_MXQ    the stored output is MX block-quantised (blocks of mx_block columns, a power of two between the
+  //                   elements of 16 bytes and 64; FP4 E2M1 elements);
   //   CONV_EPI_RESID  nothing is stored: `partial` receives, per row tile, the column sums of
   //                   resid - (x w^T + bias) and of its square (resid: [rows][cout] in the storage type).
   int epi = 0;
   const void* resid = nullptr;
+  int mx_block = 32;
   // Square dense products (n = cin = cout, k = 1) with triangular operands; the kernel then walks only the K range
   // that can hold non-zeros and returns at once in tiles that hold no wanted output (they are left unwritten):
   //   CONV_TRI_LOWER_UPPER  x lower triangular, w^T upper triangular (w[n][k] = 0 for k > n);

@@ -142,13 +142,16 @@ extern "C" int model_transform_mse(const void* x, const void* a_mat, const float
     return fail(AE_EINVAL, "model_transform_mse: null argument");
   if (dtype != AE_F32 && dtype != AE_BF16) return fail(AE_EINVAL, "model_transform_mse: bad dtype");
   if (rows <= 0 || d <= 0 || rows >= 0x7FFFFFFF || d >= 0x7FFFFFFF) return fail(AE_EINVAL, "model_transform_mse: bad size");
-  if (block != 32) return fail(AE_EINVAL, "model_transform_mse: the fused epilogue quantises blocks of 32");
+  const int epc = 16 / (int)dtype_size(dtype);
+  if (block < epc || block > 64 || (block & (block - 1)) != 0)
+    return fail(AE_EINVAL, "model_transform_mse: the fused epilogue quantises blocks of 8 (bf16) / 4 (fp32) to 64 columns, a power of two");
   hipStream_t s = (hipStream_t)stream;
   ConvArgs g1;
   memset(&g1, 0, sizeof(g1));
   g1.x = x; g1.w = a_mat; g1.bias = v; g1.y = yq;
   g1.n = (int)rows; g1.hc = g1.wc = 1; g1.cin = g1.cout = (int)d; g1.k = 1; g1.up = 0; g1.act = ACT_NONE; g1.dtype = dtype;
   g1.epi = CONV_EPI_MXQ;
+  g1.mx_block = block;
   if (!conv_epi_usable(g1))
     return fail(AE_EINVAL, "model_transform_mse: d must be a multiple of 128 and rows a multiple of the row tile (256 bf16 / 128 fp32), tensors below 2 GiB");
   // T(x) = x A^T + v, rounded to the storage type and MX-quantised in the GEMM's epilogue
