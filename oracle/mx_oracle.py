@@ -17,13 +17,23 @@ Readings where the paper is silent (each one is listed in the design document):
   * the scale exponent is clamped to the E8M0 range [-127, 127];
   * plain numpy in float64, one obviously-correct nearest-value search per element: no blocking
     tricks, no bit manipulation.
-The integer element format mentioned in the paper ("INT4" under MX scaling) is not an OCP format
-and is not built: parity unpinned.
+Other element formats (`fmt` argument of mx_quantize / quantize_element):
+  * "fp8": FP8 E4M3 of the OCP 8-bit floating point specification (bias 7, subnormals k * 2^-9, normals
+    (1 + m/8) * 2^(e-7), no infinities, the all-ones code is NaN: largest value 448 = 1.75 * 2^8), r_max = 8;
+  * "int4": the integer element format the paper evaluates under MX scaling is not an OCP format and the paper does
+    not define it — PARITY UNPINNED.  Reading, by analogy with the OCP MXINT8 element (two's complement with an
+    implied scale that puts the values in (-2, 2)): magnitudes k/4, k = 0..7, symmetric (the code -8 unused),
+    r_max = 0, round to nearest, ties to the even integer, saturating at 1.75.
 """
 import numpy as np
 
 E2M1_GRID = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0])   # index = 3-bit magnitude code (exponent:mantissa)
 E2M1_RMAX = 2
+# FP8 E4M3: index = 7-bit magnitude code (4 exponent bits : 3 mantissa bits), the NaN code 0x7F left out
+E4M3_GRID = np.array([(m / 8.0) * 2.0 ** -6 if e == 0 else (1.0 + m / 8.0) * 2.0 ** (e - 7)
+                      for e in range(16) for m in range(8)][:-1])
+INT4_GRID = np.arange(8) / 4.0                                     # reading (unpinned): see the header
+FORMATS = {"fp4": (E2M1_GRID, E2M1_RMAX), "fp8": (E4M3_GRID, 8), "int4": (INT4_GRID, 0)}
 SCALE_EXP_MIN, SCALE_EXP_MAX = -127, 127
 
 
@@ -39,13 +49,31 @@ def quantize_element_e2m1(y):
     return np.sign(y) * E2M1_GRID[pick]
 
 
-def block_scale_exponent(amax):
+def quantize_element(y, fmt="fp4"):
+    """Q_e of the named element format: nearest magnitude of its grid, ties to the even code, saturating."""
+    if fmt == "fp4":
+        return quantize_element_e2m1(y)
+    grid = FORMATS[fmt][0]
+    y = np.asarray(y, dtype=np.float64)
+    a = np.abs(y).reshape(-1)
+    out = np.empty_like(a)
+    for lo in range(0, a.size, 1 << 16):                    # (bounded memory: the grid has up to 127 entries)
+        dist = np.abs(a[lo:lo + (1 << 16), None] - grid)
+        best = dist.min(axis=-1, keepdims=True)
+        cand = dist == best
+        even = cand & (np.arange(grid.size) % 2 == 0)
+        pick = np.where(even.any(axis=-1), even.argmax(axis=-1), cand.argmax(axis=-1))
+        out[lo:lo + (1 << 16)] = grid[pick]
+    return np.sign(y) * out.reshape(y.shape)
+
+
+def block_scale_exponent(amax, r_max=E2M1_RMAX):
     """floor(log2(amax)) - r_max, clamped to the E8M0 range; amax > 0 (float64, exact via frexp)."""
     m, e = np.frexp(amax)                                   # amax = m * 2^e, 0.5 <= m < 1  =>  floor(log2 amax) = e - 1
-    return np.clip(e - 1 - E2M1_RMAX, SCALE_EXP_MIN, SCALE_EXP_MAX)
+    return np.clip(e - 1 - r_max, SCALE_EXP_MIN, SCALE_EXP_MAX)
 
 
-def mx_quantize(x, block=32):
+def mx_quantize(x, block=32, fmt="fp4"):
     """Q(x) of Eq. (1) for a [rows][d] array, blocks of `block` consecutive elements of a row."""
     x = np.asarray(x, dtype=np.float64)
     assert x.ndim == 2 and x.shape[1] % block == 0
@@ -53,9 +81,9 @@ def mx_quantize(x, block=32):
     out = np.zeros_like(xb)
     amax = np.abs(xb).max(axis=1)
     nz = amax > 0.0
-    k = block_scale_exponent(amax[nz])
+    k = block_scale_exponent(amax[nz], FORMATS[fmt][1])
     s = np.ldexp(1.0, k)[:, None]
-    out[nz] = s * quantize_element_e2m1(xb[nz] / s)
+    out[nz] = s * quantize_element(xb[nz] / s, fmt)
     return out.reshape(x.shape)
 
 

@@ -195,3 +195,54 @@ def test_transform_mse_power_of_two_gain_is_free():
     e1, eb1, _ = mx.transform_mse(x, A, v, Ainv)
     e2, eb2, _ = mx.transform_mse(x, 8.0 * A, 8.0 * v, Ainv / 8.0)
     assert np.isclose(e1, e2, rtol=1e-12) and np.allclose(eb1, eb2, rtol=1e-12)
+
+
+# ------------------------------------------------------------------ other element formats
+def test_fp8_e4m3_grid_is_the_ocp_format():
+    g = mx.E4M3_GRID
+    assert g.size == 127 and g[0] == 0.0 and np.all(np.diff(g) > 0)
+    assert g[1] == 2.0 ** -9 and g[8] == 2.0 ** -6 and g[-1] == 448.0          # smallest subnormal, smallest normal, largest
+    assert g[7] == 7 * 2.0 ** -9 and g[9] - g[8] == 2.0 ** -9                   # the subnormal spacing continues into the first binade
+    assert np.all(np.diff(g)[8:] == 2.0 ** (np.floor(np.log2(g[8:-1])) - 3))    # eight steps per binade
+    assert mx.FORMATS["fp8"][1] == 8 and 2.0 ** 8 <= g[-1] < 2.0 ** 9           # r_max: the largest binade
+
+
+@pytest.mark.parametrize("fmt", ["fp8", "int4"])
+def test_other_formats_fixed_points_idempotence_and_error_bound(fmt):
+    grid, r_max = mx.FORMATS[fmt]
+    rng = np.random.default_rng(11)
+    # every grid value times a power of two, with the block maximum in the largest binade, is a fixed point
+    blk = np.concatenate([[2.0 ** r_max], rng.choice(grid[grid < 2.0 ** (r_max + 1)], size=31) * rng.choice([-1.0, 1.0], size=31)])
+    for k in (-3, 0, 5):
+        x = (blk * 2.0 ** k)[None, :]
+        assert np.array_equal(mx.mx_quantize(x, 32, fmt), x)
+    x = rng.standard_normal((64, 64)) * np.exp(rng.standard_normal((64, 1)))
+    q = mx.mx_quantize(x, 32, fmt)
+    assert np.array_equal(mx.mx_quantize(q, 32, fmt), q)                        # idempotent
+    assert np.array_equal(mx.mx_quantize(-x, 32, fmt), -q)                      # odd
+    assert np.array_equal(mx.mx_quantize(8.0 * x, 32, fmt), 8.0 * q)            # commutes with powers of two
+    # round to nearest: the error is at most half the local spacing, except where the largest binade clips
+    s = np.repeat(mx.block_scales(x, 32) * 2.0 ** (mx.E2M1_RMAX - r_max), 32, axis=1)    # block_scales uses FP4's r_max
+    y = np.abs(x) / s
+    top = grid[-1]
+    inside = y <= top
+    idx = np.searchsorted(grid, y[inside], side="right") - 1
+    gap = np.where(idx + 1 < grid.size, grid[np.minimum(idx + 1, grid.size - 1)] - grid[idx], 0.0)
+    assert np.all(np.abs(np.abs(q[inside]) / s[inside] - y[inside]) <= gap / 2 + 1e-15)
+    assert np.all(np.abs(q[~inside]) / s[~inside] == top)
+
+
+def test_other_formats_against_exhaustive_search_and_ties():
+    for fmt in ("fp8", "int4"):
+        grid, r_max = mx.FORMATS[fmt]
+        top = 2.0 ** r_max
+        ys = np.linspace(-1.2 * grid[-1], 1.2 * grid[-1], 4001)
+        for y in ys[::7]:
+            x = np.array([[top * 1.0, y if abs(y) < 2 * top else 0.0]])          # block of two, maximum in the largest binade: s = 1
+            q = mx.mx_quantize(x, 2, fmt)[0, 1]
+            want = min(grid, key=lambda g: (abs(abs(x[0, 1]) - g), 0))           # nearest magnitude (ties checked below)
+            assert abs(abs(q) - abs(x[0, 1])) <= abs(want - abs(x[0, 1])) + 1e-15
+        mids = (grid[:-1] + grid[1:]) / 2                                         # every tie goes to the even code
+        for i, m in enumerate(mids):
+            got = mx.quantize_element(np.array([m]), fmt)[0]
+            assert got == (grid[i] if i % 2 == 0 else grid[i + 1])
