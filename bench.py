@@ -152,18 +152,18 @@ def bench_mx_quant(torch, ae, args):
     x = x.to(dtype).contiguous()
     q = torch.empty_like(x)
     for _ in range(args.warmup):
-        ae.model_mx_quantize(x, q, rows, d, block)
+        ae.model_mx_quantize_elem(x, q, rows, d, block, args.mx_elem)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        ae.model_mx_quantize(x, q, rows, d, block)
+        ae.model_mx_quantize_elem(x, q, rows, d, block, args.mx_elem)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     # the kernel's own duration: HIP events on the stream it runs on
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(args.steps):
-        ae.model_mx_quantize(x, q, rows, d, block)
+        ae.model_mx_quantize_elem(x, q, rows, d, block, args.mx_elem)
     e1.record()
     torch.cuda.synchronize()
     avg_ms = e0.elapsed_time(e1) / args.steps
@@ -174,13 +174,14 @@ def bench_mx_quant(torch, ae, args):
     sample = 32768
     xs = x[:sample].float().cpu().numpy().astype("float64")
     c0 = time.perf_counter()
-    mxo.mx_quantize(xs, block)
+    mxo.mx_quantize(xs, block, args.mx_elem)
     ct = time.perf_counter() - c0
     return {
         "metric": "tokens/sec, MX block quantisation Q(x)", "value": rows * args.steps / dt, "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
-        "config": {"workload": "mx_quant: Q(x), FP4 E2M1 elements, block 32", "tokens": rows, "d": d, "block": block},
+        "config": {"workload": "mx_quant: Q(x), %s elements, block 32" % {"fp4": "FP4 E2M1", "fp8": "FP8 E4M3", "int4": "4-bit integer"}[args.mx_elem],
+                   "tokens": rows, "d": d, "block": block},
         "roofline": {"bound": "hbm", "kernel": "k_mx_quantize", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": ach / HBM_PEAK_GBS, "traffic": MX_TRAFFIC_BYTES.get(args.dtype), "avg_ms": avg_ms,
                      "launches_per_step": 1,
@@ -567,6 +568,8 @@ def main():
     ap.add_argument("--fold", action="store_true",
                     help="benchmark the folding of two affine transformations into the four projections of one attention block "
                          "(d = 4096) instead of a network: one JSON line with roofline and cpu_baseline")
+    ap.add_argument("--mx-elem", default="fp4", choices=["fp4", "fp8", "int4"],
+                    help="element format of --mx-quant (FP4 E2M1, FP8 E4M3, or the 4-bit integer reading)")
     ap.add_argument("--calibrate-mfma", action="store_true",
                     help="only run the library's plain matrix-core loop (with and without LDS fragment reads) and exit")
     ap.add_argument("--channel-sweep", action="store_true",

@@ -185,8 +185,13 @@ int model_timing_reset(ae_model* m);
  * An all-zero block yields zeros; the scale exponent is clamped to [-127, 127].  q has the shape
  * and dtype of x and may be x itself.  d must be a positive multiple of block (32 in the paper's
  * experiments); any block size works, sizes of 8 elements (bf16) / 4 (fp32) times a power of two
- * up to 64 lanes, with 16-byte aligned pointers, take the vector path.  AE_EINVAL on bad arguments. */
+ * up to 64 lanes, with 16-byte aligned pointers, take the vector path.  AE_EINVAL on bad arguments.
+ * model_mx_quantize_elem: the same with the element format chosen (the paper names FP4, INT4 and FP8 elements):
+ *   elem 0: FP4 E2M1 as above;  2: FP8 E4M3 of the OCP 8-bit floating point specification (r_max = 8, largest value
+ *   448, subnormals below 2^-6);  1: a 4-bit integer element, which is not a standard MX format and which the paper
+ *   does not define — reading: magnitudes k/4, k = 0..7, r_max = 0, nearest, ties to even, saturating at 1.75. */
 int model_mx_quantize(const void* x, void* q, int64_t rows, int64_t d, int block, int dtype, void* stream);
+int model_mx_quantize_elem(const void* x, void* q, int64_t rows, int64_t d, int block, int elem, int dtype, void* stream);
 
 /* Transformation mean squared error of the paper (Definition "Transformation Mean Squared Error",
  * Eq. 2, and the block-wise error E_B^i of its numerical analysis) for the affine map

@@ -22,7 +22,7 @@ SYMBOLS = [
     "model_describe", "model_create", "model_destroy", "model_param_count", "model_io_shape",
     "model_set_sample_offset", "model_forward", "model_backward", "model_loss_mse", "model_noise",
     "model_pnorm_awgn", "model_gen_bits", "model_count_errors", "model_num_steps", "model_step_info",
-    "model_get_activation", "model_timing_enable", "model_set_overlap", "model_calibrate_mfma", "model_mx_quantize", "model_transform_mse_workspace",
+    "model_get_activation", "model_timing_enable", "model_set_overlap", "model_calibrate_mfma", "model_mx_quantize", "model_mx_quantize_elem", "model_transform_mse_workspace",
     "model_transform_mse", "model_lu_workspace", "model_lu_compose", "model_lu_backward", "model_vol_penalty", "model_lu_inverse_workspace", "model_lu_inverse", "model_lu_timing", "model_qr_workspace", "model_qr_compose", "model_qr_backward", "model_qr_inverse", "model_fold_workspace", "model_fold_linear", "model_fold_embedding", "model_timing_slots",
     "model_timing_read", "model_timing_reset", "model_last_error",
 ]
@@ -61,6 +61,7 @@ def _load():
     L.model_set_overlap.argtypes = [vp, C.c_int]
     L.model_calibrate_mfma.argtypes = [C.c_int, C.c_int, C.c_int, vp, C.POINTER(C.c_double), C.POINTER(C.c_double), vp]
     L.model_mx_quantize.argtypes = [vp, vp, C.c_int64, C.c_int64, C.c_int, C.c_int, vp]
+    L.model_mx_quantize_elem.argtypes = [vp, vp, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int, vp]
     L.model_transform_mse_workspace.argtypes = [C.c_int64, C.c_int64, C.c_int, i64p]
     L.model_transform_mse.argtypes = [vp, vp, vp, vp, vp, C.c_int64, C.c_int64, C.c_int, C.c_int, vp, vp, vp, vp, vp]
     L.model_lu_workspace.argtypes = [C.c_int64, C.c_int, i64p]
@@ -232,6 +233,15 @@ def model_mx_quantize(x, q, rows, d, block=32):
     dtype = AE_BF16 if x.dtype == torch.bfloat16 else AE_F32
     assert x.numel() == rows * d and q.numel() == rows * d and q.dtype == x.dtype
     _check(lib.model_mx_quantize(_ptr(x), _ptr(q), rows, d, block, dtype, _stream()))
+
+
+MX_ELEMS = {"fp4": 0, "int4": 1, "fp8": 2}
+
+
+def model_mx_quantize_elem(x, q, rows, d, block, elem):
+    dtype = AE_BF16 if x.dtype == torch.bfloat16 else AE_F32
+    assert x.numel() == rows * d and q.numel() == rows * d and q.dtype == x.dtype
+    _check(lib.model_mx_quantize_elem(_ptr(x), _ptr(q), rows, d, block, MX_ELEMS[elem] if isinstance(elem, str) else elem, dtype, _stream()))
 
 
 def model_transform_mse_workspace(rows, d, dtype):

@@ -94,10 +94,10 @@ __device__ __forceinline__ float apply_act(float v, int act) {
 
 // ---- MX block quantisation (the paper's Eq. 1) with FP4 E2M1 elements, shared by the stand-alone kernel
 // and the GEMM epilogue that quantises its output ----
-// scale exponent of a block from its largest magnitude (> 0): floor(log2 amax) - r_max (r_max = 2),
+// scale exponent of a block from its largest magnitude (> 0): floor(log2 amax) - r_max (r_max = 2 for FP4 E2M1),
 // clamped to the E8M0 range
-__device__ __forceinline__ int mx_scale_exp(float amax) {
-  int k = ilogbf(amax) - 2;                      // subnormal maxima included
+__device__ __forceinline__ int mx_scale_exp(float amax, int r_max = 2) {
+  int k = ilogbf(amax) - r_max;                  // subnormal maxima included
   k = k < -127 ? -127 : k;
   return k > 127 ? 127 : k;
 }
@@ -109,5 +109,32 @@ __device__ __forceinline__ float mx_quant_e2m1(float v, float inv_s, float s) {
   r = fminf(r, 6.0f);
   return copysignf(r, y) * s;                    // at most two significant bits times a power of two: exact
 }
+
+// Other element formats under the same block scale.  MX_FP8: FP8 E4M3 of the OCP 8-bit floating point specification
+// (subnormal spacing 2^-9 below 2^-6, three mantissa bits above, largest value 448, r_max = 8).  MX_INT4: the integer
+// element the paper evaluates is not a standard format; reading: magnitudes k/4, k = 0..7, r_max = 0, saturating at 1.75.
+enum { MX_FP4 = 0, MX_INT4 = 1, MX_FP8 = 2 };
+template <int FMT> struct MxFormat;
+template <> struct MxFormat<MX_FP4> {
+  static constexpr int r_max = 2;
+  static __device__ __forceinline__ float quant(float v, float inv_s, float s) { return mx_quant_e2m1(v, inv_s, s); }
+};
+template <> struct MxFormat<MX_INT4> {
+  static constexpr int r_max = 0;
+  static __device__ __forceinline__ float quant(float v, float inv_s, float s) {
+    const float y = v * inv_s;                   // exact, |y| < 2
+    return copysignf(fminf(rintf(fabsf(y) * 4.0f), 7.0f) * 0.25f, y) * s;
+  }
+};
+template <> struct MxFormat<MX_FP8> {
+  static constexpr int r_max = 8;
+  static __device__ __forceinline__ float quant(float v, float inv_s, float s) {
+    const float y = v * inv_s;                   // exact, |y| < 512
+    const float a = fabsf(y);
+    const int e = a < 0.015625f ? -6 : ilogbf(a);                 // binade of the value; subnormals share the spacing of 2^-6
+    const float r = rintf(a * ldexpf(1.0f, 3 - e)) * ldexpf(1.0f, e - 3);   // three mantissa bits: exact in binary32
+    return copysignf(fminf(r, 448.0f), y) * s;
+  }
+};
 
 }  // namespace ae

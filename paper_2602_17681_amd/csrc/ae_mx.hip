@@ -21,7 +21,7 @@ constexpr int NT = 256;
 
 // Vector path: a lane owns 16 bytes (V elements); the LPB = B / V lanes of a block are neighbours
 // in a wavefront and find the block maximum with xor-shuffles.
-template <typename T>
+template <typename T, int FMT>
 __global__ __launch_bounds__(NT) void k_mx_quantize(const T* x, T* q, int64_t nchunks, int lpb) {   // q may be x
   constexpr int V = Store<T>::VEC;
   const int64_t span = (int64_t)gridDim.x * NT;
@@ -41,10 +41,10 @@ __global__ __launch_bounds__(NT) void k_mx_quantize(const T* x, T* q, int64_t nc
     for (int off = 1; off < lpb; off <<= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
     float o[V];
     if (amax > 0.0f) {
-      const int k = mx_scale_exp(amax);
+      const int k = mx_scale_exp(amax, MxFormat<FMT>::r_max);
       const float s = ldexpf(1.0f, k), inv_s = ldexpf(1.0f, -k);
 #pragma unroll
-      for (int j = 0; j < V; ++j) o[j] = mx_quant_e2m1(v[j], inv_s, s);
+      for (int j = 0; j < V; ++j) o[j] = MxFormat<FMT>::quant(v[j], inv_s, s);
     } else {
 #pragma unroll
       for (int j = 0; j < V; ++j) o[j] = 0.0f;
@@ -54,7 +54,7 @@ __global__ __launch_bounds__(NT) void k_mx_quantize(const T* x, T* q, int64_t nc
 }
 
 // Any other block size or alignment: one thread per block, two passes over its elements.
-template <typename T>
+template <typename T, int FMT>
 __global__ void k_mx_quantize_generic(const T* x, T* q, int64_t nblocks, int block) {
   for (int64_t b = (int64_t)blockIdx.x * NT + threadIdx.x; b < nblocks; b += (int64_t)gridDim.x * NT) {
     const T* xb = x + b * block;
@@ -62,16 +62,16 @@ __global__ void k_mx_quantize_generic(const T* x, T* q, int64_t nblocks, int blo
     float amax = 0.0f;
     for (int j = 0; j < block; ++j) amax = fmaxf(amax, fabsf(Store<T>::ld(xb + j)));
     if (amax > 0.0f) {
-      const int k = mx_scale_exp(amax);
+      const int k = mx_scale_exp(amax, MxFormat<FMT>::r_max);
       const float s = ldexpf(1.0f, k), inv_s = ldexpf(1.0f, -k);
-      for (int j = 0; j < block; ++j) Store<T>::st(qb + j, mx_quant_e2m1(Store<T>::ld(xb + j), inv_s, s));
+      for (int j = 0; j < block; ++j) Store<T>::st(qb + j, MxFormat<FMT>::quant(Store<T>::ld(xb + j), inv_s, s));
     } else {
       for (int j = 0; j < block; ++j) Store<T>::st(qb + j, 0.0f);
     }
   }
 }
 
-template <typename T>
+template <typename T, int FMT>
 int launch_mx(const void* x, void* q, int64_t total, int block, hipStream_t s) {
   constexpr int V = Store<T>::VEC;
   const int lpb = block / V;
@@ -81,12 +81,12 @@ int launch_mx(const void* x, void* q, int64_t total, int block, hipStream_t s) {
     const int64_t nchunks = total / V;
     int64_t g = (nchunks + NT - 1) / NT;
     if (g > 256 * 32) g = 256 * 32;                       // 32 workgroups per compute unit, then rounds
-    hipLaunchKernelGGL((k_mx_quantize<T>), dim3((unsigned)g), dim3(NT), 0, s, (const T*)x, (T*)q, nchunks, lpb);
+    hipLaunchKernelGGL((k_mx_quantize<T, FMT>), dim3((unsigned)g), dim3(NT), 0, s, (const T*)x, (T*)q, nchunks, lpb);
   } else {
     const int64_t nblocks = total / block;
     int64_t g = (nblocks + NT - 1) / NT;
     if (g > 65535) g = 65535;
-    hipLaunchKernelGGL((k_mx_quantize_generic<T>), dim3((unsigned)g), dim3(NT), 0, s, (const T*)x, (T*)q, nblocks, block);
+    hipLaunchKernelGGL((k_mx_quantize_generic<T, FMT>), dim3((unsigned)g), dim3(NT), 0, s, (const T*)x, (T*)q, nblocks, block);
   }
   return launch_status("mx_quantize");
 }
@@ -171,13 +171,26 @@ extern "C" int model_transform_mse(const void* x, const void* a_mat, const float
   return launch_status("transform_mse");
 }
 
-extern "C" int model_mx_quantize(const void* x, void* q, int64_t rows, int64_t d, int block, int dtype, void* stream) {
+extern "C" int model_mx_quantize_elem(const void* x, void* q, int64_t rows, int64_t d, int block, int elem, int dtype, void* stream) {
   using namespace ae;
   if (!x || !q) return fail(AE_EINVAL, "model_mx_quantize: null argument");
   if (rows < 0 || d <= 0 || block < 1 || d % block != 0) return fail(AE_EINVAL, "model_mx_quantize: d must be a positive multiple of block");
   if (dtype != AE_F32 && dtype != AE_BF16) return fail(AE_EINVAL, "model_mx_quantize: bad dtype");
+  if (elem != MX_FP4 && elem != MX_INT4 && elem != MX_FP8) return fail(AE_EINVAL, "model_mx_quantize: bad element format");
   if (rows > ((int64_t)1 << 40) / d) return fail(AE_EINVAL, "model_mx_quantize: tensor too large");
   if (rows == 0) return AE_OK;
   hipStream_t s = (hipStream_t)stream;
-  return dtype == AE_BF16 ? launch_mx<bf16_t>(x, q, rows * d, block, s) : launch_mx<float>(x, q, rows * d, block, s);
+  const int64_t n = rows * d;
+  if (dtype == AE_BF16) {
+    if (elem == MX_FP4) return launch_mx<bf16_t, MX_FP4>(x, q, n, block, s);
+    if (elem == MX_INT4) return launch_mx<bf16_t, MX_INT4>(x, q, n, block, s);
+    return launch_mx<bf16_t, MX_FP8>(x, q, n, block, s);
+  }
+  if (elem == MX_FP4) return launch_mx<float, MX_FP4>(x, q, n, block, s);
+  if (elem == MX_INT4) return launch_mx<float, MX_INT4>(x, q, n, block, s);
+  return launch_mx<float, MX_FP8>(x, q, n, block, s);
+}
+
+extern "C" int model_mx_quantize(const void* x, void* q, int64_t rows, int64_t d, int block, int dtype, void* stream) {
+  return model_mx_quantize_elem(x, q, rows, d, block, 0, dtype, stream);
 }

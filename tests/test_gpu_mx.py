@@ -118,6 +118,36 @@ def test_full_size_sampled_rows(ae, dtype):
     assert bool(torch.isin(ratio, grid).all())
 
 
+# ------------------------------------------------------------------ other element formats
+@pytest.mark.parametrize("elem", ["fp8", "int4"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("rows,d,block", [(37, 1024, 32), (64, 2560, 32), (16, 320, 160), (128, 512, 16)])
+def test_other_element_formats_bit_exact(ae, elem, dtype, rows, d, block):
+    """FP8 E4M3 and the 4-bit integer reading: every operation of the kernel is exact in binary32, as for FP4."""
+    import torch
+    bf = dtype == "bf16"
+    x = wl.make_activations(rows, d, seed=rows + block, bf16=bf)
+    x[0, :block] = 0.0                                              # an all-zero block
+    x[1, 0] = 448.0 * 2.0 ** 20                                     # large and tiny blocks
+    x[2, :block] *= 2.0 ** -60
+    xt = torch.from_numpy(x).cuda().to(torch.bfloat16 if bf else torch.float32)
+    qt = torch.full_like(xt, float("nan"))
+    ae.model_mx_quantize_elem(xt, qt, rows, d, block, elem)
+    ref = mxo.mx_quantize(xt.float().cpu().numpy().astype(np.float64), block, elem).astype(np.float32)
+    assert _same_bits(qt.float().cpu().numpy(), ref)
+    q2 = torch.empty_like(qt)
+    ae.model_mx_quantize_elem(qt, q2, rows, d, block, elem)
+    assert torch.equal(q2, qt)                                      # idempotent
+
+
+def test_element_format_argument_check(ae):
+    import torch
+    t = torch.zeros(64, device="cuda")
+    p = C.c_void_p(t.data_ptr())
+    assert ae.lib.model_mx_quantize_elem(p, p, 2, 32, 32, 3, 0, None) == -1
+    assert ae.lib.model_mx_quantize_elem(p, p, 2, 32, 32, 2, 0, None) == 0
+
+
 # ------------------------------------------------------------------ transformation mean squared error (Eq. 2)
 def _run_tmse(ae, x, a, v, ainv, ishift, dtype, block=32):
     import torch
