@@ -210,6 +210,11 @@ int model_transform_mse_workspace(int64_t rows, int64_t d, int dtype, int64_t* b
 int model_transform_mse(const void* x, const void* a_mat, const float* v, const void* a_inv, const float* inv_shift,
                         int64_t rows, int64_t d, int block, int dtype, void* yq, void* workspace, float* e_blocks,
                         float* e_total, void* stream);
+/* The same with the element format of Q chosen as in model_mx_quantize_elem (0 FP4 E2M1, 1 the 4-bit integer
+ * reading, 2 FP8 E4M3). */
+int model_transform_mse_elem(const void* x, const void* a_mat, const float* v, const void* a_inv, const float* inv_shift,
+                             int64_t rows, int64_t d, int block, int elem, int dtype, void* yq, void* workspace,
+                             float* e_blocks, float* e_total, void* stream);
 
 /* LU parametrisation of a learnable invertible matrix (the paper's Section on learning affine transformations,
  * Eq. 4):  A = P L (U + diag(s)).  Free parameters (device pointers, binary32 master copies): lp, up [d][d]

@@ -114,7 +114,7 @@ def _round_bf16(a):
     return u.astype(np.uint32).view(np.float32).reshape(np.shape(a)).astype(np.float64)
 
 
-def transform_mse(x, A, v, Ainv, block=32, storage="f64"):
+def transform_mse(x, A, v, Ainv, block=32, storage="f64", fmt="fp4"):
     """Returns (E, E_blocks[d / block], yq) for tokens x [n][d]; storage in {"f64", "f32", "bf16"}."""
     x = np.asarray(x, dtype=np.float64)
     A = np.asarray(A, dtype=np.float64)
@@ -126,7 +126,7 @@ def transform_mse(x, A, v, Ainv, block=32, storage="f64"):
         y = _round_bf16(y)
     elif storage == "f32":
         y = y.astype(np.float32).astype(np.float64)
-    yq = mx_quantize(y, block)
+    yq = mx_quantize(y, block, fmt)
     xhat = yq @ Ainv.T - Ainv @ v                          # T^-1(Q(T(x)))
     err2 = (x - xhat) ** 2
     e_blocks = err2.reshape(n, d // block, block).sum(axis=2).mean(axis=0) / block

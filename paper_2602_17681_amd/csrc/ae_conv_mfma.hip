@@ -57,7 +57,7 @@ struct IgemmParams {
   //   2: nothing is stored; the epilogue forms resid[m][n] - (acc + bias) and leaves per-tile column sums of it
   //      and of its square in `partial` (resid: [M][N] in the storage type)
   const void* resid;
-  int mx_block;
+  int mx_block, mx_elem;       // block size and element format (MX_FP4 / MX_INT4 / MX_FP8) of epilogue 1
   // Square dense products (M = N = K) with triangular operands: K range per tile, and tiles nobody wants skipped.
   //   1: x[m][k] = 0 for k > m and w[n][k] = 0 for k > n (lower times upper): K ends at min(last row, last column) + 1
   //   2: x[m][k] = 0 for k < m, wanted outputs n >= m: K starts at the tile's first row; tiles below the diagonal return
@@ -164,10 +164,12 @@ __device__ __forceinline__ void igemm_store_interior(const floatx16 (&acc)[MI][N
         for (int t = 0; t < EPC; ++t) amax = fmaxf(amax, fabsf(f[t]));
         for (int off = 1; off < p.mx_block / EPC; off <<= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
         if (amax > 0.0f) {
-          const int k = mx_scale_exp(amax);
+          const int k = mx_scale_exp(amax, p.mx_elem == MX_FP8 ? 8 : (p.mx_elem == MX_INT4 ? 0 : 2));
           const float sc = ldexpf(1.0f, k), inv_sc = ldexpf(1.0f, -k);
 #pragma unroll
-          for (int t = 0; t < EPC; ++t) f[t] = mx_quant_e2m1(f[t], inv_sc, sc);
+          for (int t = 0; t < EPC; ++t)
+            f[t] = p.mx_elem == MX_FP8 ? MxFormat<MX_FP8>::quant(f[t], inv_sc, sc)
+                                       : (p.mx_elem == MX_INT4 ? MxFormat<MX_INT4>::quant(f[t], inv_sc, sc) : mx_quant_e2m1(f[t], inv_sc, sc));
         }
         Store<T>::stv(dst, f);
       } else {
@@ -968,6 +970,7 @@ bool conv_epi_usable(const ConvArgs& a) {
   if (a.epi == CONV_EPI_MXQ) {
     const int epc = 16 / (int)dtype_size(a.dtype);
     if (a.mx_block < epc || a.mx_block > 64 || (a.mx_block & (a.mx_block - 1)) != 0) return false;
+    if (a.mx_elem != MX_FP4 && a.mx_elem != MX_INT4 && a.mx_elem != MX_FP8) return false;
   }
   const IgemmTile t = pick_tile(a.n, a.cout, a.cin, (int)dtype_size(a.dtype));
   return (t.bn == 128 || t.bn == 256) && a.n % t.bm == 0;
@@ -994,6 +997,7 @@ int launch_conv_mfma(const ConvArgs& a0, hipStream_t s) {
   p.Hv = a.hc; p.Wv = a.wc; p.stride = 1; p.pad = (a.k - 1) >> 1; p.phases = 1;
   p.resid = a0.resid;
   p.mx_block = a0.mx_block;
+  p.mx_elem = a0.mx_elem;
   p.tri = a0.tri;
   p.tri_b = a0.tri_b;
   if (a0.tri >= 8 && (a0.tri > 10 || a.dtype != AE_F32 || a0.tri_b < 128 || a0.tri_b % 128 != 0 || a.n % (2 * a0.tri_b) != 0))

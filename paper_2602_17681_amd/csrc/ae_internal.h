@@ -147,6 +147,7 @@ struct ConvArgs {
   int epi = 0;
   const void* resid = nullptr;
   int mx_block = 32;
+  int mx_elem = 0;                 // element format of CONV_EPI_MXQ: 0 FP4 E2M1, 1 the 4-bit integer reading, 2 FP8 E4M3
   // Square dense products (n = cin = cout, k = 1) with triangular operands; the kernel then walks only the K range
   // that can hold non-zeros and returns at once in tiles that hold no wanted output (they are left unwritten):
   //   CONV_TRI_LOWER_UPPER  x lower triangular, w^T upper triangular (w[n][k] = 0 for k > n);

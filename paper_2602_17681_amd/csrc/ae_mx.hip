@@ -134,10 +134,21 @@ extern "C" int model_transform_mse_workspace(int64_t rows, int64_t d, int dtype,
   return AE_OK;
 }
 
+extern "C" int model_transform_mse_elem(const void* x, const void* a_mat, const float* v, const void* a_inv, const float* inv_shift,
+                                        int64_t rows, int64_t d, int block, int elem, int dtype, void* yq, void* workspace,
+                                        float* e_blocks, float* e_total, void* stream);
+
 extern "C" int model_transform_mse(const void* x, const void* a_mat, const float* v, const void* a_inv, const float* inv_shift,
                                    int64_t rows, int64_t d, int block, int dtype, void* yq, void* workspace,
                                    float* e_blocks, float* e_total, void* stream) {
+  return model_transform_mse_elem(x, a_mat, v, a_inv, inv_shift, rows, d, block, 0, dtype, yq, workspace, e_blocks, e_total, stream);
+}
+
+extern "C" int model_transform_mse_elem(const void* x, const void* a_mat, const float* v, const void* a_inv, const float* inv_shift,
+                                        int64_t rows, int64_t d, int block, int elem, int dtype, void* yq, void* workspace,
+                                        float* e_blocks, float* e_total, void* stream) {
   using namespace ae;
+  if (elem != MX_FP4 && elem != MX_INT4 && elem != MX_FP8) return fail(AE_EINVAL, "model_transform_mse: bad element format");
   if (!x || !a_mat || !v || !a_inv || !inv_shift || !yq || !workspace || !e_blocks || !e_total)
     return fail(AE_EINVAL, "model_transform_mse: null argument");
   if (dtype != AE_F32 && dtype != AE_BF16) return fail(AE_EINVAL, "model_transform_mse: bad dtype");
@@ -152,6 +163,7 @@ extern "C" int model_transform_mse(const void* x, const void* a_mat, const float
   g1.n = (int)rows; g1.hc = g1.wc = 1; g1.cin = g1.cout = (int)d; g1.k = 1; g1.up = 0; g1.act = ACT_NONE; g1.dtype = dtype;
   g1.epi = CONV_EPI_MXQ;
   g1.mx_block = block;
+  g1.mx_elem = elem;
   if (!conv_epi_usable(g1))
     return fail(AE_EINVAL, "model_transform_mse: d must be a multiple of 128 and rows a multiple of the row tile (256 bf16 / 128 fp32), tensors below 2 GiB");
   // T(x) = x A^T + v, rounded to the storage type and MX-quantised in the GEMM's epilogue

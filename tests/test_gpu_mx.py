@@ -149,7 +149,7 @@ def test_element_format_argument_check(ae):
 
 
 # ------------------------------------------------------------------ transformation mean squared error (Eq. 2)
-def _run_tmse(ae, x, a, v, ainv, ishift, dtype, block=32):
+def _run_tmse(ae, x, a, v, ainv, ishift, dtype, block=32, elem=None):
     import torch
     td = torch.bfloat16 if dtype == "bf16" else torch.float32
     rows, d = x.shape
@@ -160,7 +160,7 @@ def _run_tmse(ae, x, a, v, ainv, ishift, dtype, block=32):
     ws = torch.empty(ae.model_transform_mse_workspace(rows, d, ae.DTYPES[dtype]) // 4, dtype=torch.float32, device="cuda")
     eb = torch.full((d // block,), float("nan"), device="cuda")
     et = torch.full((1,), float("nan"), device="cuda")
-    ae.model_transform_mse(xt, at, vt, ait, st, rows, d, block, yq, ws, eb, et)
+    ae.model_transform_mse(xt, at, vt, ait, st, rows, d, block, yq, ws, eb, et, elem)
     torch.cuda.synchronize()
     return float(et.item()), eb.cpu().numpy().astype(np.float64), yq.float().cpu().numpy()
 
@@ -207,6 +207,24 @@ def test_transform_mse_other_block_sizes(ae, dtype, block):
         eye = np.eye(d, dtype=np.float32)
         _, _, yqi = _run_tmse(ae, xi, eye, np.zeros(d, np.float32), eye, np.zeros(d, np.float32), dtype, block)
         assert _same_bits(yqi, mxo.mx_quantize(xi.astype(np.float64), block).astype(np.float32))    # identity: plain Q(x), bit for bit
+
+
+@pytest.mark.parametrize("elem", ["fp8", "int4"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_transform_mse_other_element_formats(ae, elem, dtype):
+    bf = dtype == "bf16"
+    rows, d = 512, 256
+    x = wl.make_activations(rows, d, seed=5, bf16=bf)
+    a, v, ainv, ishift = wl.make_transform(d, seed=6, bf16=bf, kind="affine")
+    e, eb, yq = _run_tmse(ae, x, a, v, ainv, ishift, dtype, 32, elem)
+    e_o, eb_o, yq_o = mxo.transform_mse(x, a, v, ainv, 32, storage=dtype, fmt=elem)
+    tol, frac = TMSE_TOL[dtype]
+    # FP8 elements keep four significant bits: in bf16 storage (eight) the quantiser rarely moves a value at all, the
+    # error is small and dominated by the few elements near a rounding boundary: a looser relative bar on E
+    rel = 10 * tol if elem == "fp8" else tol
+    assert np.mean(yq != yq_o.astype(np.float32)) <= frac
+    assert abs(e - e_o) <= rel * e_o, (e, e_o)
+    assert abs(eb.mean() - e) <= 1e-5 * e
 
 
 def test_block_size_sweep_on_outlier_heavy_activations(ae):
