@@ -171,7 +171,7 @@ def bench_mx_quant(torch, ae, args):
     ach = nbytes / avg_ms / 1e6
     # oracle on a bounded sample of the same tensor
     import oracle.mx_oracle as mxo
-    sample = 32768
+    sample = 256 if args.no_cpu_baseline else 32768
     xs = x[:sample].float().cpu().numpy().astype("float64")
     c0 = time.perf_counter()
     mxo.mx_quantize(xs, block, args.mx_elem)
