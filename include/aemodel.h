@@ -242,8 +242,10 @@ int model_vol_penalty(const float* log_s, int64_t d, float* value, float* d_log_
 /* The inverse of the parametrised matrix, A^-1 = (U + diag s)^-1 L^-1 P^T (what the transformation error and the
  * folding take beside A): a_inv_out [d][d] in dtype.  Both triangular factors are inverted by a blocked recursion
  * (128 x 128 diagonal blocks by substitution, then neighbouring blocks merged, three launches per level), all in
- * binary32 on the matrix cores; s must not contain zeros.  d: 128 times a power of two, at most 16384.
- * workspace: model_lu_inverse_workspace bytes (six d x d binary32 matrices), 16-byte aligned. */
+ * binary32 on the matrix cores; s must not contain zeros.  d: a multiple of 128, at most 16384.  The recursion works
+ * at dp = 128 times the smallest power of two that reaches d, on the factors extended by an identity block (a width
+ * of 3 072 costs what 4 096 costs); the last product and the output are d x d again.
+ * workspace: model_lu_inverse_workspace bytes (six dp x dp binary32 matrices), 16-byte aligned. */
 int model_lu_inverse_workspace(int64_t d, int64_t* bytes);
 int model_lu_inverse(const float* lp, const float* up, const float* log_s, const float* sign_s, const int* perm, int64_t d,
                      int dtype, void* a_inv_out, void* workspace, void* stream);
@@ -267,7 +269,7 @@ int model_lu_timing(int enable, double* gemm_ms, int64_t* launches);
  *   elsewhere) and d_log_s [d] in binary32.
  * model_qr_inverse   A^-1 = (R + diag s)^-1 Q^T into a_inv_out [d][d] in dtype: Q is read from qr_workspace (the
  *   workspace model_qr_compose left, same parameters and squarings), the triangular factor is inverted as in
- *   model_lu_inverse; d: 128 times a power of two; workspace: model_lu_inverse_workspace(d) bytes. */
+ *   model_lu_inverse; d: a multiple of 128; workspace: model_lu_inverse_workspace(d) bytes. */
 int model_qr_workspace(int64_t d, int squarings, int64_t* bytes);
 int model_qr_compose(const float* g, const float* rp, const float* log_s, const float* sign_s, int64_t d, int dtype,
                      int squarings, void* a_out, void* workspace, void* stream);

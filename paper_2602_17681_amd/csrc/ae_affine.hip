@@ -227,23 +227,25 @@ void launch_build(const LuSrc& q, void* out, hipStream_t s) {
 //     T' = -(M21 X11)^T  into the upper blocks of a scratch matrix,   X21 = X22 T'^T  in place into X,
 //     X21^T = T' X22^T  in place into X^T.
 
-// entry (r, c) of the lower triangular matrix: WHICH 0: L; 1: (U + diag s)^T
+// entry (r, c) of the lower triangular matrix: WHICH 0: L; 1: (U + diag s)^T.  Rows and columns past d belong to
+// the identity block that pads the matrix to the working size of the recursion.
 template <int WHICH>
 __device__ __forceinline__ float tri_elem(const LuSrc& q, int r, int c) {
   if (c > r) return 0.0f;
+  if (r >= q.d) return r == c ? 1.0f : 0.0f;
   if (WHICH == 0) return c < r ? q.lp[(int64_t)r * q.d + c] : 1.0f;
   return c < r ? q.up[(int64_t)c * q.d + r] : q.sign[c] * expf(q.log_s[c]);
 }
 
-// mneg = -M (full d x d), x = xt = 0: 32 x 32 tiles
+// mneg = -M (full dp x dp), x = xt = 0: 32 x 32 tiles
 template <int WHICH>
-__global__ __launch_bounds__(256) void k_tri_prepare(LuSrc q, float* __restrict__ mneg, float* __restrict__ x, float* __restrict__ xt) {
+__global__ __launch_bounds__(256) void k_tri_prepare(LuSrc q, int dp, float* __restrict__ mneg, float* __restrict__ x, float* __restrict__ xt) {
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
   const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const int r = r0 + ty + 8 * j, c = c0 + tx;
-    const int64_t i = (int64_t)r * q.d + c;
+    const int64_t i = (int64_t)r * dp + c;
     // (U + diag s)^T is read along its columns: the tile is small enough for the cache to absorb the stride
     mneg[i] = -tri_elem<WHICH>(q, r, c);
     x[i] = 0.0f;
@@ -256,7 +258,7 @@ __global__ __launch_bounds__(256) void k_tri_prepare(LuSrc q, float* __restrict_
 // of merges [[X11, 0], [-X22 M21 X11, X22]] with all threads sharing the outputs of the two small products.  The
 // block and its transpose are written into the full matrices x and xt.
 template <int WHICH>
-__global__ __launch_bounds__(256) void k_tri_diag_inverse(LuSrc q, float* __restrict__ x, float* __restrict__ xt) {
+__global__ __launch_bounds__(256) void k_tri_diag_inverse(LuSrc q, int dp, float* __restrict__ x, float* __restrict__ xt) {
   __shared__ float mb[128][129];
   __shared__ float xb[128][129];
   __shared__ float tb[64 * 64];                        // M21 X11 of every pair of the current level: pairs * b * b = 64 b values
@@ -310,20 +312,29 @@ __global__ __launch_bounds__(256) void k_tri_diag_inverse(LuSrc q, float* __rest
   }
   for (int e = tid; e < 128 * 128; e += 256) {
     const int i = e >> 7, j = e & 127;
-    x[(int64_t)(o + i) * q.d + o + j] = xb[i][j];
-    xt[(int64_t)(o + i) * q.d + o + j] = xb[j][i];
+    x[(int64_t)(o + i) * dp + o + j] = xb[i][j];
+    xt[(int64_t)(o + i) * dp + o + j] = xb[j][i];
   }
 }
 
-// out[r][c] = z[r][perm[c]] in the storage type (z P^T)
+// out[r][c] = z[r][perm[c]] in the storage type (z P^T); z has rows of dp entries, out is d x d
 template <typename T>
-__global__ __launch_bounds__(256) void k_lu_inverse_out(const float* __restrict__ z, const int* __restrict__ perm, int d, T* __restrict__ out) {
+__global__ __launch_bounds__(256) void k_lu_inverse_out(const float* __restrict__ z, const int* __restrict__ perm, int d, int dp, T* __restrict__ out) {
   const int64_t n = (int64_t)d * d;
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
     const int r = (int)(i / d), c = (int)(i - (int64_t)r * d);
     int src = perm[c];
     if ((unsigned)src >= (unsigned)d) src = c;                         // not a permutation: stay inside the arrays
-    Store<T>::st(out + i, z[(int64_t)r * d + src]);
+    Store<T>::st(out + i, z[(int64_t)r * dp + src]);
+  }
+}
+
+// dst [d][d] = the leading d x d part of src, whose rows hold dp entries (both multiples of 128: 16-byte vectors)
+__global__ __launch_bounds__(256) void k_tri_compact(const float* __restrict__ src, int dp, int d, float* __restrict__ dst) {
+  const int64_t n4 = (int64_t)d * (d / 4);
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256) {
+    const int r = (int)(i / (d / 4)), c4 = (int)(i - (int64_t)r * (d / 4));
+    reinterpret_cast<float4*>(dst)[i] = *reinterpret_cast<const float4*>(src + (int64_t)r * dp + 4 * c4);
   }
 }
 
@@ -370,19 +381,29 @@ unsigned lu_grid(int64_t items) {
   return (unsigned)(g < 4096 ? (g < 1 ? 1 : g) : 4096);
 }
 
-// the blocked recursion above for one lower triangular matrix: x = M^-1 and xt = its transpose ([d][d] binary32 each);
+// 128 times the smallest power of two that reaches d: the working size of the recursion
+int64_t tri_padded_size(int64_t d) {
+  int64_t dp = 128;
+  while (dp < d) dp *= 2;
+  return dp;
+}
+
+// the blocked recursion above for one lower triangular matrix, padded with an identity block to the working size
+// d = dp (128 times a power of two, at least q.d): x = M^-1 and xt = its transpose ([dp][dp] binary32 each);
 // mneg and tt are scratch of the same size
 template <int WHICH>
-int tri_inverse(const LuSrc& q, float* mneg, float* tt, float* x, float* xt, hipStream_t s) {
-  const int d = q.d;
-  hipLaunchKernelGGL((k_tri_prepare<WHICH>), dim3(d / 32, d / 32), dim3(256), 0, s, q, mneg, x, xt);
-  hipLaunchKernelGGL((k_tri_diag_inverse<WHICH>), dim3(d / 128), dim3(256), 0, s, q, x, xt);
+int tri_inverse(const LuSrc& q, int dp, float* mneg, float* tt, float* x, float* xt, hipStream_t s) {
+  const int d = dp;
+  hipLaunchKernelGGL((k_tri_prepare<WHICH>), dim3(d / 32, d / 32), dim3(256), 0, s, q, d, mneg, x, xt);
+  hipLaunchKernelGGL((k_tri_diag_inverse<WHICH>), dim3(d / 128), dim3(256), 0, s, q, d, x, xt);
   AE_TRY(launch_status("tri_diag_inverse"));
   for (int b = 128; b < d; b *= 2) {
     ConvArgs a;
     memset(&a, 0, sizeof(a));
     a.n = d; a.hc = a.wc = 1; a.cin = a.cout = d; a.k = 1; a.up = 0; a.act = ACT_NONE; a.dtype = AE_F32;
     a.tri_b = b;
+    a.tri_pairs = (q.d + 2 * b - 1) / (2 * b);                            // pairs wholly inside the identity padding stay as they are
+    a.tri_d = q.d < d ? q.d : 0;                                          // ... and so do the zero parts of the last pair
     a.x = xt; a.w = mneg; a.y = tt; a.tri = CONV_TRI_PAIR_UPPER_K0;       // T' = X11^T (-M21)^T = -(M21 X11)^T
     AE_TRY(launch_conv_mfma(a, s));
     a.x = x; a.w = tt; a.y = x; a.tri = CONV_TRI_PAIR_LOWER_K1;           // X21 = X22 T'^T (reads the diagonal blocks of x, writes below them)
@@ -662,17 +683,21 @@ extern "C" int model_qr_inverse(const float* rp, const float* log_s, const float
   using namespace ae;
   if (!rp || !log_s || !sign_s || !qr_workspace || !a_inv_out || !workspace) return fail(AE_EINVAL, "model_qr_inverse: null argument");
   AE_TRY(check_qr_args("model_qr_inverse", d, dtype, squarings));
-  if (d < 128 || d % 128 != 0 || ((d / 128) & (d / 128 - 1)) != 0)
-    return fail(AE_EINVAL, "model_qr_inverse: d must be 128 times a power of two, at most 16384");
+  if (d < 128 || d % 128 != 0) return fail(AE_EINVAL, "model_qr_inverse: d must be a multiple of 128, at most 16384");
   if (((reinterpret_cast<uintptr_t>(workspace) | reinterpret_cast<uintptr_t>(qr_workspace) | reinterpret_cast<uintptr_t>(a_inv_out)) & 15) != 0)
     return fail(AE_EINVAL, "model_qr_inverse: the matrices and the workspaces must be 16-byte aligned");
   hipStream_t s = (hipStream_t)stream;
-  const int64_t dd = d * d;
+  const int64_t dd = d * d, dp = tri_padded_size(d), pp = dp * dp;
   const QrSlots w{const_cast<float*>(reinterpret_cast<const float*>(qr_workspace)), dd, squarings};
   float* f = reinterpret_cast<float*>(workspace);
-  float *mneg = f, *tt = f + dd, *rdinv_t = f + 2 * dd, *rdinv = f + 3 * dd, *z = f + 4 * dd;
+  float *mneg = f, *tt = f + pp, *rdinv_t = f + 2 * pp, *rdinv = f + 3 * pp, *z = f + 4 * pp;
   LuSrc q{nullptr, rp, log_s, sign_s, nullptr, nullptr, (int)d};
-  AE_TRY(tri_inverse<1>(q, mneg, tt, rdinv_t, rdinv, s));                 // ((R + diag s)^T)^-1 and its transpose (R + diag s)^-1
+  AE_TRY(tri_inverse<1>(q, (int)dp, mneg, tt, rdinv_t, rdinv, s));        // ((R + diag s)^T)^-1 and its transpose (R + diag s)^-1
+  if (dp != d) {                                                          // drop the identity padding
+    hipLaunchKernelGGL(k_tri_compact, dim3(lu_grid(dd)), dim3(256), 0, s, (const float*)rdinv, (int)dp, (int)d, mneg);
+    AE_TRY(launch_status("tri_compact"));
+    rdinv = mneg;
+  }
   // A^-1 = (R + diag s)^-1 Q^T = x w^T with w = Q
   if (dtype == AE_F32) return dense_product(rdinv, w.q(squarings), a_inv_out, (int)d, AE_F32, CONV_TRI_NONE, s);
   AE_TRY(dense_product(rdinv, w.q(squarings), z, (int)d, AE_F32, CONV_TRI_NONE, s));
@@ -683,9 +708,9 @@ extern "C" int model_qr_inverse(const float* rp, const float* log_s, const float
 extern "C" int model_lu_inverse_workspace(int64_t d, int64_t* bytes) {
   using namespace ae;
   if (!bytes) return fail(AE_EINVAL, "model_lu_inverse_workspace: null argument");
-  if (d < 128 || d > 16384 || d % 128 != 0 || ((d / 128) & (d / 128 - 1)) != 0)
-    return fail(AE_EINVAL, "model_lu_inverse_workspace: d must be 128 times a power of two, at most 16384");
-  *bytes = 6 * d * d * 4 + 1024;
+  if (d < 128 || d > 16384 || d % 128 != 0) return fail(AE_EINVAL, "model_lu_inverse_workspace: d must be a multiple of 128, at most 16384");
+  const int64_t dp = tri_padded_size(d);
+  *bytes = 6 * dp * dp * 4 + 1024;
   return AE_OK;
 }
 
@@ -694,25 +719,31 @@ extern "C" int model_lu_inverse(const float* lp, const float* up, const float* l
   using namespace ae;
   if (!lp || !up || !log_s || !sign_s || !perm || !a_inv_out || !workspace) return fail(AE_EINVAL, "model_lu_inverse: null argument");
   if (dtype != AE_F32 && dtype != AE_BF16) return fail(AE_EINVAL, "model_lu_inverse: bad dtype");
-  if (d < 128 || d > 16384 || d % 128 != 0 || ((d / 128) & (d / 128 - 1)) != 0)
-    return fail(AE_EINVAL, "model_lu_inverse: d must be 128 times a power of two, at most 16384");
+  if (d < 128 || d > 16384 || d % 128 != 0) return fail(AE_EINVAL, "model_lu_inverse: d must be a multiple of 128, at most 16384");
   if ((reinterpret_cast<uintptr_t>(workspace) & 15) != 0) return fail(AE_EINVAL, "model_lu_inverse: the workspace must be 16-byte aligned");
   hipStream_t s = (hipStream_t)stream;
-  const int64_t dd = d * d;
+  const int64_t dd = d * d, dp = tri_padded_size(d), pp = dp * dp;
   float* f = reinterpret_cast<float*>(workspace);
-  float* mneg = f;                  // -M of the factor being inverted; afterwards (U + diag s)^-1 L^-1
-  float* tt = f + dd;               // scratch of the recursion
-  float* linv = f + 2 * dd;         // L^-1 and its transpose
-  float* linv_t = f + 3 * dd;
-  float* udinv_t = f + 4 * dd;      // ((U + diag s)^T)^-1 = ((U + diag s)^-1)^T and its transpose (U + diag s)^-1
-  float* udinv = f + 5 * dd;
+  float* mneg = f;                  // -M of the factor being inverted; afterwards scratch
+  float* tt = f + pp;               // scratch of the recursion
+  float* linv = f + 2 * pp;         // L^-1 and its transpose; afterwards (U + diag s)^-1 L^-1
+  float* linv_t = f + 3 * pp;
+  float* udinv_t = f + 4 * pp;      // ((U + diag s)^T)^-1 = ((U + diag s)^-1)^T and its transpose (U + diag s)^-1
+  float* udinv = f + 5 * pp;
   LuSrc q{lp, up, log_s, sign_s, nullptr, nullptr, (int)d};
-  AE_TRY(tri_inverse<0>(q, mneg, tt, linv, linv_t, s));
-  AE_TRY(tri_inverse<1>(q, mneg, tt, udinv_t, udinv, s));
-  float* z = mneg;
+  AE_TRY(tri_inverse<0>(q, (int)dp, mneg, tt, linv, linv_t, s));
+  AE_TRY(tri_inverse<1>(q, (int)dp, mneg, tt, udinv_t, udinv, s));
+  if (dp != d) {                    // drop the identity padding: the two factors of the last product as d x d matrices
+    hipLaunchKernelGGL(k_tri_compact, dim3(lu_grid(dd)), dim3(256), 0, s, (const float*)udinv, (int)dp, (int)d, mneg);
+    hipLaunchKernelGGL(k_tri_compact, dim3(lu_grid(dd)), dim3(256), 0, s, (const float*)linv_t, (int)dp, (int)d, tt);
+    AE_TRY(launch_status("tri_compact"));
+    udinv = mneg;
+    linv_t = tt;
+  }
+  float* z = linv;
   AE_TRY(dense_product(udinv, linv_t, z, (int)d, AE_F32, CONV_TRI_UPPER_LOWER, s));
-  if (dtype == AE_BF16) hipLaunchKernelGGL((k_lu_inverse_out<bf16_t>), dim3(lu_grid(dd)), dim3(256), 0, s, (const float*)z, perm, (int)d, (bf16_t*)a_inv_out);
-  else hipLaunchKernelGGL((k_lu_inverse_out<float>), dim3(lu_grid(dd)), dim3(256), 0, s, (const float*)z, perm, (int)d, (float*)a_inv_out);
+  if (dtype == AE_BF16) hipLaunchKernelGGL((k_lu_inverse_out<bf16_t>), dim3(lu_grid(dd)), dim3(256), 0, s, (const float*)z, perm, (int)d, (int)d, (bf16_t*)a_inv_out);
+  else hipLaunchKernelGGL((k_lu_inverse_out<float>), dim3(lu_grid(dd)), dim3(256), 0, s, (const float*)z, perm, (int)d, (int)d, (float*)a_inv_out);
   return launch_status("lu_inverse_out");
 }
 

@@ -67,7 +67,9 @@ struct IgemmParams {
   // tri_b): only the tiles of one off-diagonal block per pair are computed, over the K range of one block:
   //   8: tile rows in an even block r, columns in block r+1, K = block r;   10: the same tiles, K = block r+1;
   //   9: tile rows in an odd block r, columns in block r-1, K = block r
-  int tri, tri_b;
+  // tri_d > 0 (modes 8-10): the matrices are an identity block beyond row and column tri_d; tiles of the odd block that
+  // lie wholly beyond it return (their outputs are zero and stay unwritten) and K ranges over the odd block end at tri_d.
+  int tri, tri_b, tri_d;
 };
 
 // output row (pixel index in y) of GEMM row m
@@ -475,6 +477,10 @@ __global__ __launch_bounds__(WGM * WGN * 64) __attribute__((amdgpu_waves_per_eu(
     if (p.tri == 9 ? !((rb & 1) == 1 && cb == rb - 1) : !((rb & 1) == 0 && cb == rb + 1)) return;
     k_lo = (p.tri == 10 ? rb + 1 : rb) * p.tri_b;
     k_hi = k_lo + p.tri_b;
+    if (p.tri_d > 0) {
+      if ((p.tri == 9 ? m0 : (int64_t)n0) >= p.tri_d) return;
+      if (p.tri != 8) k_hi = min(k_hi, p.tri_d);
+    }
   }
   const int kt_lo = k_lo / BK, kt_hi = (k_hi + BK - 1) / BK;
   const int kt0 = INTERIOR ? kt_lo : max(kt_lo, split * p.slabs_per_split);   // first K slab of this workgroup
@@ -1000,7 +1006,9 @@ int launch_conv_mfma(const ConvArgs& a0, hipStream_t s) {
   p.mx_elem = a0.mx_elem;
   p.tri = a0.tri;
   p.tri_b = a0.tri_b;
-  if (a0.tri >= 8 && (a0.tri > 10 || a.dtype != AE_F32 || a0.tri_b < 128 || a0.tri_b % 128 != 0 || a.n % (2 * a0.tri_b) != 0))
+  p.tri_d = a0.tri >= 8 ? a0.tri_d : 0;
+  if (a0.tri >= 8 && (a0.tri > 10 || a.dtype != AE_F32 || a0.tri_b < 128 || a0.tri_b % 128 != 0 || a.n % (2 * a0.tri_b) != 0 ||
+                      a0.tri_d < 0 || a0.tri_d > a.n || a0.tri_d % 128 != 0))
     return fail(AE_EINVAL, "conv_mfma: bad block size for the blocked triangular inverse");
   if (a0.tri != 0 && (a0.tri < 0 || (a0.tri > 4 && a0.tri < 8) || a0.tri > 10 || a.k != 1 || a.hc != 1 || a.wc != 1 || a.up != 0 || a.n != a.cout || a.cin != a.cout ||
                       a0.epi != CONV_EPI_NONE || a.partial))
@@ -1049,7 +1057,11 @@ int launch_conv_mfma(const ConvArgs& a0, hipStream_t s) {
   splits = (KT + p.slabs_per_split - 1) / p.slabs_per_split;
   p.split_out = splits > 1 ? a.splitk_ws : nullptr;
   dim3 grid((unsigned)(tiles_m * p.tiles_n * splits * p.phases));
-  if (a0.tri >= 8) grid = dim3((unsigned)((p.M / (2 * a0.tri_b)) * (a0.tri_b / t.bm) * (a0.tri_b / t.bn)));
+  if (a0.tri >= 8) {
+    const int64_t all_pairs = p.M / (2 * a0.tri_b);
+    const int64_t pairs = a0.tri_pairs > 0 && a0.tri_pairs < all_pairs ? a0.tri_pairs : all_pairs;
+    grid = dim3((unsigned)(pairs * (a0.tri_b / t.bm) * (a0.tri_b / t.bn)));
+  }
   const bool interior = splits == 1 && p.M % t.bm == 0 && p.N % t.bn == 0 && !a.y_aux && a.act != ACT_SIGMOID &&
                         !(a.partial && a.act != ACT_NONE);
 #define IGEMM_LAUNCH_K(T, BMV, BNV, GM, GN, KB)                                                        \

@@ -160,8 +160,13 @@ struct ConvArgs {
   //                           UPPER_K0: rows in block r, columns in block r+1, K = block r;
   //                           UPPER_K1: the same tiles, K = block r+1;
   //                           LOWER_K1: rows in block r+1, columns in block r, K = block r+1.
+  //                         tri_pairs > 0 limits the launch to the first tri_pairs pairs (the rest keep their contents).
   int tri = 0;
   int tri_b = 0;
+  //                         tri_d > 0 (a multiple of 128): the matrices are an identity block beyond row and column
+  //                         tri_d; tiles and K ranges beyond it are skipped (outputs there are zero, left unwritten).
+  int tri_pairs = 0;
+  int tri_d = 0;
 };
 enum { CONV_TRI_NONE = 0, CONV_TRI_LOWER_UPPER = 1, CONV_TRI_UPPER_X = 2, CONV_TRI_UPPER_W = 3, CONV_TRI_UPPER_LOWER = 4,
        CONV_TRI_PAIR_UPPER_K0 = 8, CONV_TRI_PAIR_LOWER_K1 = 9, CONV_TRI_PAIR_UPPER_K1 = 10 };

@@ -160,11 +160,13 @@ def _inverse(ae, params, d, dtype):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("d,kind", [(128, "random"), (256, "random"), (512, "bd_hadamard"), (1024, "random"), (2048, "bd_hadamard")])
+@pytest.mark.parametrize("d,kind", [(128, "random"), (256, "random"), (384, "random"), (512, "bd_hadamard"), (640, "bd_hadamard"),
+                                    (1024, "random"), (1408, "random"), (2048, "bd_hadamard")])
 def test_inverse_matches_the_inverse_of_the_composed_matrix(ae, d, kind, dtype):
     """A^-1 from the triangular factors against numpy's inverse of the oracle's A (float64).  The blocked recursion
     runs in binary32: its error is a few 1e-7 times the condition number of the factors (below 1e2 here), so the
-    binary32 result is held to 1e-4 and the bf16 result to the rounding of the output."""
+    binary32 result is held to 1e-4 and the bf16 result to the rounding of the output.  Sizes that are not 128 times a
+    power of two (3, 5 and 11 blocks of 128) run the recursion padded with an identity block."""
     params = wl.make_lu_params(d, seed=d + 7, kind=kind, noise=1e-3 if kind == "bd_hadamard" else 0.0)
     a = ao.lu_compose(*params)
     ref = np.linalg.inv(a)
@@ -182,6 +184,16 @@ def test_inverse_full_size(ae):
     got = _inverse(ae, params, d, "bf16")
     assert _close(got, np.linalg.inv(a), TOL["bf16"])
     got32 = _inverse(ae, params, d, "f32")
+    assert np.abs(a @ got32 - np.eye(d)).max() < 1e-4
+
+
+def test_inverse_at_a_width_of_three_blocks_of_1024(ae):
+    """d = 3 072 (a residual width of the paper's model family that is not 128 times a power of two)."""
+    d = 3072
+    params = wl.make_lu_params(d, seed=13, kind="bd_hadamard", noise=1e-3)
+    a = ao.lu_compose(*params)
+    got32 = _inverse(ae, params, d, "f32")
+    assert _close(got32, np.linalg.inv(a), TOL["f32"])
     assert np.abs(a @ got32 - np.eye(d)).max() < 1e-4
 
 
@@ -231,10 +243,12 @@ def test_inverse_argument_checks(ae):
     t = torch.zeros(128 * 128, device="cuda")
     p = C.c_void_p(t.data_ptr())
     n = C.c_int64()
-    assert ae.lib.model_lu_inverse_workspace(384, C.byref(n)) == -1        # 3 blocks: not a power of two
+    assert ae.lib.model_lu_inverse_workspace(192, C.byref(n)) == -1        # not a multiple of 128
     assert ae.lib.model_lu_inverse_workspace(64, C.byref(n)) == -1
+    assert ae.lib.model_lu_inverse_workspace(16384 + 128, C.byref(n)) == -1
     assert ae.lib.model_lu_inverse_workspace(256, C.byref(n)) == 0 and n.value == 6 * 256 * 256 * 4 + 1024
-    assert ae.lib.model_lu_inverse(p, p, p, p, p, 384, 0, p, p, None) == -1
+    assert ae.lib.model_lu_inverse_workspace(384, C.byref(n)) == 0 and n.value == 6 * 512 * 512 * 4 + 1024   # padded to 4 blocks
+    assert ae.lib.model_lu_inverse(p, p, p, p, p, 192, 0, p, p, None) == -1
     assert ae.lib.model_lu_inverse(p, p, p, p, p, 128, 3, p, p, None) == -1
     assert ae.lib.model_lu_inverse(None, p, p, p, p, 128, 0, p, p, None) == -1
 
@@ -298,10 +312,10 @@ def test_qr_full_size(ae):
     assert _close(dg, r_g, TOL["f32"]) and _close(dr, r_r, TOL["f32"]) and _close(dls, r_ls, TOL["f32"])
 
 
+@pytest.mark.parametrize("d", [512, 384])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_qr_inverse_matches_the_inverse_of_the_composed_matrix(ae, dtype):
+def test_qr_inverse_matches_the_inverse_of_the_composed_matrix(ae, dtype, d):
     import torch
-    d = 512
     td = torch.bfloat16 if dtype == "bf16" else torch.float32
     params = wl.make_qr_params(d, seed=31)
     params = (params[0] * 2.0,) + tuple(params[1:])
@@ -316,7 +330,7 @@ def test_qr_inverse_matches_the_inverse_of_the_composed_matrix(ae, dtype):
     assert _close(ainv.float().cpu().numpy().astype(np.float64), ref, TOL[dtype])
     assert ae.lib.model_qr_inverse(None, None, None, 512, 0, 5, None, None, None, None) == -1
     p = C.c_void_p(ws.data_ptr())
-    assert ae.lib.model_qr_inverse(p, p, p, 384, 0, 5, p, p, p, None) == -1       # 3 blocks: not a power of two
+    assert ae.lib.model_qr_inverse(p, p, p, 192, 0, 5, p, p, p, None) == -1       # not a multiple of 128
 
 
 def test_qr_more_squarings_for_a_large_generator(ae):
