@@ -127,7 +127,19 @@ def transform_mse(x, A, v, Ainv, block=32, storage="f64", fmt="fp4"):
     elif storage == "f32":
         y = y.astype(np.float32).astype(np.float64)
     yq = mx_quantize(y, block, fmt)
+    e, e_blocks = reconstruction_error(x, yq, v, Ainv, block)
+    return e, e_blocks, yq
+
+
+def reconstruction_error(x, yq, v, Ainv, block=32):
+    """The second half of Eq. 2 on given quantised values yq = Q(T(x)) [n][d]: (E, E_blocks[d / block]) of
+    x - T^-1(yq).  Separate so that a test can hold a device's error sums against its own quantisation decisions."""
+    x = np.asarray(x, dtype=np.float64)
+    yq = np.asarray(yq, dtype=np.float64)
+    Ainv = np.asarray(Ainv, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    n, d = x.shape
     xhat = yq @ Ainv.T - Ainv @ v                          # T^-1(Q(T(x)))
     err2 = (x - xhat) ** 2
     e_blocks = err2.reshape(n, d // block, block).sum(axis=2).mean(axis=0) / block
-    return float(err2.sum() / (n * d)), e_blocks, yq
+    return float(err2.sum() / (n * d)), e_blocks

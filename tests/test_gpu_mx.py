@@ -172,7 +172,8 @@ TMSE_TOL = {"f32": (1e-4, 1e-4), "bf16": (5e-3, 3e-3)}
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("rows,d,kind", [(256, 128, "identity"), (512, 256, "hadamard"), (768, 384, "affine"), (1024, 1024, "affine")])
+@pytest.mark.parametrize("rows,d,kind", [(256, 128, "identity"), (512, 256, "hadamard"), (768, 384, "affine"), (1024, 1024, "affine"),
+                                         (512, 3072, "affine"), (256, 5120, "affine")])
 def test_transform_mse_matches_oracle(ae, dtype, rows, d, kind):
     bf = dtype == "bf16"
     x = wl.make_activations(rows, d, seed=rows + d, bf16=bf)
@@ -183,7 +184,15 @@ def test_transform_mse_matches_oracle(ae, dtype, rows, d, kind):
     differ = np.mean(yq != yq_o.astype(np.float32))
     assert differ <= frac, differ
     assert abs(e - e_o) <= tol * e_o, (e, e_o)
-    assert np.all(np.abs(eb - eb_o) <= 2 * tol * eb_o + 1e-30), np.max(np.abs(eb - eb_o) / eb_o)
+    if differ == 0.0:
+        assert np.all(np.abs(eb - eb_o) <= 2 * tol * eb_o + 1e-30), np.max(np.abs(eb - eb_o) / eb_o)
+    else:
+        # a value that falls on the other side of a rounding boundary moves its whole token's reconstruction (A^-1 is
+        # dense), hence every block's sum by O(1 / rows): the block sums are held to the tolerance against the oracle's
+        # second half on the device's own decisions, and only coarsely against the oracle's decisions
+        _, eb_own = mxo.reconstruction_error(x, yq, v, ainv, 32)
+        assert np.all(np.abs(eb - eb_own) <= 2 * tol * eb_own + 1e-30), np.max(np.abs(eb - eb_own) / eb_own)
+        assert np.all(np.abs(eb - eb_o) <= 2e-2 * eb_o), np.max(np.abs(eb - eb_o) / eb_o)
     assert abs(eb.mean() - e) <= 1e-5 * e
     if kind == "identity":
         assert _same_bits(yq, mxo.mx_quantize(x.astype(np.float64), 32).astype(np.float32))       # T = id: plain Q(x), bit for bit
