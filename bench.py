@@ -264,7 +264,7 @@ def bench_lu_param(torch, ae, args):
     d x d matrix, d = 4 096: compose A from the free parameters, the volume regulariser and its gradient, and the
     parameter gradients from dLoss/dA.  Algorithmic FLOPs: three products with a triangular factor of which (backward)
     a triangle is wanted, 2 d^3 / 3 each."""
-    d = 4096
+    d = args.width
     bf = args.dtype == "bf16"
     td = torch.bfloat16 if bf else torch.float32
     params = wl.make_lu_params(d, seed=11, kind="bd_hadamard", noise=1e-3)
@@ -306,7 +306,7 @@ def bench_lu_param(torch, ae, args):
     avg_ms = gemm_ms / max(launches, 1)
     # beside the step: the inverse of the same matrix (what the transformation error and the folding take with A)
     inv_ms = None
-    if d % 128 == 0 and (d // 128) & (d // 128 - 1) == 0:
+    if d % 128 == 0:
         ainv = torch.empty((d, d), dtype=td, device="cuda")
         wsi = torch.empty(ae.model_lu_inverse_workspace(d), dtype=torch.uint8, device="cuda")
         for _ in range(3):
@@ -335,16 +335,16 @@ def bench_lu_param(torch, ae, args):
     except Exception:
         cores = 1
     return {
-        "metric": "matrices/sec, LU-parametrised 4096 x 4096 matrix: compose + regulariser + parameter gradients",
+        "metric": "matrices/sec, LU-parametrised %d x %d matrix: compose + regulariser + parameter gradients" % (d, d),
         "value": args.steps / dt, "unit": "matrices/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": args.dtype, "data": "synthetic",
-        "config": {"workload": "lu_param: A = P L (U + diag s), d = 4096, block-Hadamard initialisation + noise", "d": d,
+        "config": {"workload": "lu_param: A = P L (U + diag s), d = %d, block-Hadamard initialisation + noise" % d, "d": d,
                    "inverse_ms_beside_the_step": inv_ms},
         # the three GEMM launches of a step (62 % of its kernel time; twelve element-wise kernels are the rest)
         "roofline": {"bound": "mfma", "kernel": "k_igemm (triangular K ranges)", "achieved": ach, "peak": PEAK[args.dtype],
                      "unit": "TFLOP/s", "frac": ach / PEAK[args.dtype], "achieved_whole_step": flops / step_ms / 1e9,
-                     "traffic": LU_TRAFFIC_BYTES.get(args.dtype), "avg_ms": avg_ms, "launches_per_step": 3,
+                     "traffic": LU_TRAFFIC_BYTES.get(args.dtype) if d == 4096 else None, "avg_ms": avg_ms, "launches_per_step": 3,
                      "flops_per_launch": flops / 3, "bytes_per_launch": 3.0 * d * d * es, "step_ms_under_events": step_ms},
         "cpu_baseline": {"value": reps / ct, "unit": "matrices/s", "cores": cores, "kind": "oracle",
                          "sample": "%d full steps (d = 4096, float64) in %.1f s" % (reps, ct)},
@@ -562,6 +562,8 @@ def main():
     ap.add_argument("--lu-param", action="store_true",
                     help="benchmark the LU parametrisation of Eq. (4) (compose, regulariser, parameter gradients; d = 4096) "
                          "instead of a network: one JSON line with roofline and cpu_baseline")
+    ap.add_argument("--width", type=int, default=4096, metavar="D",
+                    help="--lu-param: the matrix size d (a multiple of 32; the inverse is timed beside the step for multiples of 128)")
     ap.add_argument("--qr-param", action="store_true",
                     help="benchmark the QR parametrisation of Eq. (5) (matrix exponential by scaling and squaring, d = 4096; "
                          "at most 5 timed steps) instead of a network: one JSON line with roofline and cpu_baseline")
