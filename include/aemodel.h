@@ -229,7 +229,9 @@ int model_transform_mse_elem(const void* x, const void* a_mat, const float* v, c
  * model_lu_compose  writes a_out = A [d][d] in dtype.
  * model_lu_backward given g = dLoss/dA [d][d] in dtype, writes the gradients of the free parameters in binary32:
  *   d_lp [d][d] (strictly lower part, zero elsewhere), d_up [d][d] (strictly upper part, zero elsewhere),
- *   d_log_s [d].  The products are rounded to dtype before they are cut to the triangles.
+ *   d_log_s [d].  The products are rounded to dtype before they are cut to the triangles.  The lower-triangle
+ *   branch runs on a stream the library owns (default priority), forked from and joined back into `stream` inside
+ *   the call: for the caller everything is ordered on `stream` as usual.
  * model_vol_penalty the volume regulariser in the form used in practice (Eq. 6 and the paragraph after it):
  *   *value = (sum_i log_s[i])^2 (device pointer), d_log_s (device, nullable) its gradient 2 sum. */
 int model_lu_workspace(int64_t d, int dtype, int64_t* bytes);
@@ -243,9 +245,11 @@ int model_vol_penalty(const float* log_s, int64_t d, float* value, float* d_log_
  * folding take beside A): a_inv_out [d][d] in dtype.  Both triangular factors are inverted by a blocked recursion
  * (128 x 128 diagonal blocks by substitution, then neighbouring blocks merged, three launches per level), all in
  * binary32 on the matrix cores; s must not contain zeros.  d: a multiple of 128, at most 16384.  The recursion works
- * at dp = 128 times the smallest power of two that reaches d, on the factors extended by an identity block (a width
- * of 3 072 costs what 4 096 costs); the last product and the output are d x d again.
- * workspace: model_lu_inverse_workspace bytes (six dp x dp binary32 matrices), 16-byte aligned. */
+ * at dp = 128 times the smallest power of two that reaches d, on the factors extended by an identity block (pairs,
+ * tiles and K ranges wholly inside the padding are skipped); the last product and the output are d x d again.
+ * workspace: model_lu_inverse_workspace bytes (eight dp x dp binary32 matrices), 16-byte aligned.  The two
+ * triangular inversions run side by side, one of them on a stream the library owns, forked from and joined back
+ * into `stream` inside the call. */
 int model_lu_inverse_workspace(int64_t d, int64_t* bytes);
 int model_lu_inverse(const float* lp, const float* up, const float* log_s, const float* sign_s, const int* perm, int64_t d,
                      int dtype, void* a_inv_out, void* workspace, void* stream);

@@ -15,6 +15,7 @@
 #include <stdint.h>
 #include <string.h>
 
+#include <mutex>
 #include "ae_device.h"
 #include "ae_internal.h"
 
@@ -356,6 +357,49 @@ double g_timing_ms = 0.0;
 int64_t g_timing_launches = 0;
 hipEvent_t g_ev0 = nullptr, g_ev1 = nullptr;
 
+// one stream of the library's own (default priority, created on first use, kept until the process ends) for work that
+// runs beside the caller's stream; null if it cannot be created (the callers then stay on one stream)
+hipStream_t lu_side_stream() {
+  static std::once_flag once;
+  static hipStream_t side = nullptr;
+  std::call_once(once, [] {
+    if (hipStreamCreateWithFlags(&side, hipStreamNonBlocking) != hipSuccess) side = nullptr;
+  });
+  return side;
+}
+
+// A second branch of work beside the caller's stream: begin() forks the library's stream from `main` (events are per
+// call, so calls from several host threads only share the stream), end() joins it back — also after an error, so that
+// `main` always covers both branches.  Disabled (or no stream to be had): side == main, everything stays in order.
+struct SideBranch {
+  hipStream_t main = nullptr, side = nullptr;
+  hipEvent_t fork = nullptr, join = nullptr;
+  int begin(hipStream_t s, bool enable, const char* who) {
+    main = side = s;
+    hipStream_t s2 = enable ? lu_side_stream() : nullptr;
+    if (!s2) return AE_OK;
+    if (hipEventCreateWithFlags(&fork, hipEventDisableTiming) != hipSuccess) { fork = nullptr; return fail(AE_EHIP, "%s: cannot create an event", who); }
+    if (hipEventCreateWithFlags(&join, hipEventDisableTiming) != hipSuccess || hipEventRecord(fork, s) != hipSuccess ||
+        hipStreamWaitEvent(s2, fork, 0) != hipSuccess) {
+      (void)hipEventDestroy(fork);
+      if (join) (void)hipEventDestroy(join);
+      fork = join = nullptr;
+      return fail(AE_EHIP, "%s: cannot fork the side stream", who);
+    }
+    side = s2;
+    return AE_OK;
+  }
+  int end(int rc, const char* who) {
+    if (!fork) return rc;
+    const bool joined = hipEventRecord(join, side) == hipSuccess && hipStreamWaitEvent(main, join, 0) == hipSuccess;
+    (void)hipEventDestroy(fork);                // (released by the runtime once the recorded work has completed)
+    (void)hipEventDestroy(join);
+    fork = join = nullptr;
+    if (!joined && rc == AE_OK) rc = fail(AE_EHIP, "%s: cannot join the side stream", who);
+    return rc;
+  }
+};
+
 // y[m][n] = sum_k x[m][k] w[n][k], all d x d in the storage type; tri: which operand is triangular (CONV_TRI_*)
 int dense_product(const void* x, const void* w, void* y, int d, int dtype, int tri, hipStream_t s) {
   ConvArgs a;
@@ -561,25 +605,35 @@ extern "C" int model_lu_backward(const void* g, const float* lp, const float* up
   hipLaunchKernelGGL(k_lu_iota, dim3(pg), dim3(256), 0, s, inv, (int)d);
   hipLaunchKernelGGL(k_lu_invert_perm, dim3(pg), dim3(256), 0, s, perm, inv, (int)d);
   LuSrc q{lp, up, log_s, sign_s, inv, g, (int)d};
-  if (dtype == AE_BF16) {
-    launch_build_transposed<bf16_t, LU_L>(q, lt, s); launch_build_transposed<bf16_t, LU_B>(q, bt, s);
-    launch_build_rows<bf16_t, LU_UD>(q, ud, s); launch_build_rows<bf16_t, LU_B>(q, b, s);
-  } else {
-    launch_build_transposed<float, LU_L>(q, lt, s); launch_build_transposed<float, LU_B>(q, bt, s);
-    launch_build_rows<float, LU_UD>(q, ud, s); launch_build_rows<float, LU_B>(q, b, s);
-  }
-  AE_TRY(launch_status("lu_build"));
-  AE_TRY(dense_product(lt, bt, dud, (int)d, dtype, CONV_TRI_UPPER_X, s));
-  AE_TRY(dense_product(b, ud, dl, (int)d, dtype, CONV_TRI_UPPER_W, s));
+  // The two gradient branches share nothing but their inputs, and a product with triangular K ranges ends on a few long
+  // tiles that leave most of the chip idle: the lower-triangle branch runs on a stream of the library's own beside the
+  // upper-triangle branch (not while model_lu_timing brackets every product with events on one stream).
+  SideBranch br;
+  AE_TRY(br.begin(s, !g_timing, "model_lu_backward"));
+  hipStream_t s2 = br.side;
+  int rc = AE_OK;
   const unsigned grid = lu_grid(d * d / 8 * 4);
   if (dtype == AE_BF16) {
-    hipLaunchKernelGGL((k_lu_grad_upper<bf16_t>), dim3(grid), dim3(256), 0, s, (const bf16_t*)dud, log_s, sign_s, (int)d, d_up, d_log_s);
-    hipLaunchKernelGGL((k_lu_grad_lower<bf16_t>), dim3(grid), dim3(256), 0, s, (const bf16_t*)dl, (int)d, d_lp);
+    launch_build_transposed<bf16_t, LU_L>(q, lt, s); launch_build_transposed<bf16_t, LU_B>(q, bt, s);
+    launch_build_rows<bf16_t, LU_UD>(q, ud, s2); launch_build_rows<bf16_t, LU_B>(q, b, s2);
   } else {
-    hipLaunchKernelGGL((k_lu_grad_upper<float>), dim3(grid), dim3(256), 0, s, (const float*)dud, log_s, sign_s, (int)d, d_up, d_log_s);
-    hipLaunchKernelGGL((k_lu_grad_lower<float>), dim3(grid), dim3(256), 0, s, (const float*)dl, (int)d, d_lp);
+    launch_build_transposed<float, LU_L>(q, lt, s); launch_build_transposed<float, LU_B>(q, bt, s);
+    launch_build_rows<float, LU_UD>(q, ud, s2); launch_build_rows<float, LU_B>(q, b, s2);
   }
-  return launch_status("lu_backward");
+  rc = launch_status("lu_build");
+  if (rc == AE_OK) rc = dense_product(lt, bt, dud, (int)d, dtype, CONV_TRI_UPPER_X, s);
+  if (rc == AE_OK) rc = dense_product(b, ud, dl, (int)d, dtype, CONV_TRI_UPPER_W, s2);
+  if (rc == AE_OK) {
+    if (dtype == AE_BF16) {
+      hipLaunchKernelGGL((k_lu_grad_upper<bf16_t>), dim3(grid), dim3(256), 0, s, (const bf16_t*)dud, log_s, sign_s, (int)d, d_up, d_log_s);
+      hipLaunchKernelGGL((k_lu_grad_lower<bf16_t>), dim3(grid), dim3(256), 0, s2, (const bf16_t*)dl, (int)d, d_lp);
+    } else {
+      hipLaunchKernelGGL((k_lu_grad_upper<float>), dim3(grid), dim3(256), 0, s, (const float*)dud, log_s, sign_s, (int)d, d_up, d_log_s);
+      hipLaunchKernelGGL((k_lu_grad_lower<float>), dim3(grid), dim3(256), 0, s2, (const float*)dl, (int)d, d_lp);
+    }
+    rc = launch_status("lu_backward");
+  }
+  return br.end(rc, "model_lu_backward");
 }
 
 extern "C" int model_qr_workspace(int64_t d, int squarings, int64_t* bytes) {
@@ -710,7 +764,7 @@ extern "C" int model_lu_inverse_workspace(int64_t d, int64_t* bytes) {
   if (!bytes) return fail(AE_EINVAL, "model_lu_inverse_workspace: null argument");
   if (d < 128 || d > 16384 || d % 128 != 0) return fail(AE_EINVAL, "model_lu_inverse_workspace: d must be a multiple of 128, at most 16384");
   const int64_t dp = tri_padded_size(d);
-  *bytes = 6 * dp * dp * 4 + 1024;
+  *bytes = 8 * dp * dp * 4 + 1024;
   return AE_OK;
 }
 
@@ -724,15 +778,21 @@ extern "C" int model_lu_inverse(const float* lp, const float* up, const float* l
   hipStream_t s = (hipStream_t)stream;
   const int64_t dd = d * d, dp = tri_padded_size(d), pp = dp * dp;
   float* f = reinterpret_cast<float*>(workspace);
-  float* mneg = f;                  // -M of the factor being inverted; afterwards scratch
-  float* tt = f + pp;               // scratch of the recursion
+  float* mneg = f;                  // -M of the factor being inverted and the scratch of its recursion: for L ...
+  float* tt = f + pp;
   float* linv = f + 2 * pp;         // L^-1 and its transpose; afterwards (U + diag s)^-1 L^-1
   float* linv_t = f + 3 * pp;
   float* udinv_t = f + 4 * pp;      // ((U + diag s)^T)^-1 = ((U + diag s)^-1)^T and its transpose (U + diag s)^-1
   float* udinv = f + 5 * pp;
+  float* mneg_u = f + 6 * pp;       // ... and for (U + diag s)^T: the two inversions run side by side on two streams
+  float* tt_u = f + 7 * pp;         // (the lower levels of the recursion have too few tiles to fill the chip alone)
   LuSrc q{lp, up, log_s, sign_s, nullptr, nullptr, (int)d};
-  AE_TRY(tri_inverse<0>(q, (int)dp, mneg, tt, linv, linv_t, s));
-  AE_TRY(tri_inverse<1>(q, (int)dp, mneg, tt, udinv_t, udinv, s));
+  SideBranch br;
+  AE_TRY(br.begin(s, !g_timing, "model_lu_inverse"));
+  int rc = tri_inverse<0>(q, (int)dp, mneg, tt, linv, linv_t, s);
+  if (rc == AE_OK) rc = tri_inverse<1>(q, (int)dp, mneg_u, tt_u, udinv_t, udinv, br.side);
+  rc = br.end(rc, "model_lu_inverse");
+  if (rc != AE_OK) return rc;
   if (dp != d) {                    // drop the identity padding: the two factors of the last product as d x d matrices
     hipLaunchKernelGGL(k_tri_compact, dim3(lu_grid(dd)), dim3(256), 0, s, (const float*)udinv, (int)dp, (int)d, mneg);
     hipLaunchKernelGGL(k_tri_compact, dim3(lu_grid(dd)), dim3(256), 0, s, (const float*)linv_t, (int)dp, (int)d, tt);

@@ -136,6 +136,36 @@ def test_product_timing_counts_launches_and_changes_nothing(ae):
     assert ae.model_lu_timing(False) == (0.0, 0)
 
 
+def test_backward_on_two_streams_back_to_back_same_bits(ae):
+    """model_lu_backward runs its two branches on two streams.  Eight calls in a row on one workspace with changing
+    gradients, no synchronisation between them, against the same calls made one product at a time on one stream
+    (the timing mode): identical bits."""
+    import torch
+    d = 1024
+    params = wl.make_lu_params(d, seed=5)
+    dev = _dev(ae, params)
+    rng = np.random.default_rng(2)
+    gs = [torch.from_numpy(rng.standard_normal((d, d)).astype(np.float32)).cuda().to(torch.bfloat16) for _ in range(8)]
+    ws = torch.empty(ae.model_lu_workspace(d, ae.DTYPES["bf16"]), dtype=torch.uint8, device="cuda")
+
+    def run():
+        outs = [[torch.full((d, d), float("nan"), device="cuda"), torch.full((d, d), float("nan"), device="cuda"),
+                 torch.full((d,), float("nan"), device="cuda")] for _ in gs]
+        for g, o in zip(gs, outs):
+            ae.model_lu_backward(g, *dev, d, o[0], o[1], o[2], ws)
+        torch.cuda.synchronize()
+        return outs
+
+    two = run()
+    ae.model_lu_timing(True)
+    one = run()
+    ae.model_lu_timing(False)
+    for a, b in zip(two, one):
+        for x, y in zip(a, b):
+            assert torch.equal(x, y)
+    assert not torch.equal(two[0][0], two[1][0])
+
+
 def test_full_size_compose_and_backward(ae):
     """d = 4 096 in bf16, the launch bench.py times, every element against the oracle."""
     d = 4096
@@ -246,8 +276,8 @@ def test_inverse_argument_checks(ae):
     assert ae.lib.model_lu_inverse_workspace(192, C.byref(n)) == -1        # not a multiple of 128
     assert ae.lib.model_lu_inverse_workspace(64, C.byref(n)) == -1
     assert ae.lib.model_lu_inverse_workspace(16384 + 128, C.byref(n)) == -1
-    assert ae.lib.model_lu_inverse_workspace(256, C.byref(n)) == 0 and n.value == 6 * 256 * 256 * 4 + 1024
-    assert ae.lib.model_lu_inverse_workspace(384, C.byref(n)) == 0 and n.value == 6 * 512 * 512 * 4 + 1024   # padded to 4 blocks
+    assert ae.lib.model_lu_inverse_workspace(256, C.byref(n)) == 0 and n.value == 8 * 256 * 256 * 4 + 1024
+    assert ae.lib.model_lu_inverse_workspace(384, C.byref(n)) == 0 and n.value == 8 * 512 * 512 * 4 + 1024   # padded to 4 blocks
     assert ae.lib.model_lu_inverse(p, p, p, p, p, 192, 0, p, p, None) == -1
     assert ae.lib.model_lu_inverse(p, p, p, p, p, 128, 3, p, p, None) == -1
     assert ae.lib.model_lu_inverse(None, p, p, p, p, 128, 0, p, p, None) == -1
