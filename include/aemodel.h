@@ -263,9 +263,9 @@ int model_lu_timing(int enable, double* gemm_ms, int64_t* launches);
  *     Q = exp((G - G^T) / 2),   A = Q (R + diag(s)).
  * Free parameters (device, binary32 master copies): g [d][d] (only its skew-symmetric part acts), rp [d][d] of which
  * the strictly upper part is read, log_s, sign_s [d] as for the LU form.  The exponential is scaling and squaring
- * in binary32 on the matrix cores: X = S / 2^squarings, a Taylor polynomial of order 10 in Horner form, then
+ * in binary32 on the matrix cores: X = S / 2^squarings, a Taylor polynomial of order 8 in Horner form, then
  * `squarings` squarings; choose squarings with 2^squarings >= 2 ||S||_2 (5 covers ||S|| <= 16; 0 .. 16 accepted).
- * d: a multiple of 32, 32..16384.  workspace: model_qr_workspace bytes ((18 + 2 squarings) d x d binary32 matrices),
+ * d: a multiple of 32, 32..16384.  workspace: model_qr_workspace bytes ((16 + 2 squarings) d x d binary32 matrices),
  * 16-byte aligned like every [d][d] array.
  * model_qr_compose   writes a_out = A [d][d] in dtype and leaves the intermediate matrices in the workspace.
  * model_qr_backward  given g_a = dLoss/dA [d][d] in dtype and THE SAME workspace, untouched since model_qr_compose

@@ -463,7 +463,7 @@ int tri_inverse(const LuSrc& q, int dp, float* mneg, float* tt, float* x, float*
 // (H_M = I + X/M, H_k = I + X H_{k+1} / k), then J squarings — all binary32 products on the matrix cores
 // (y = x w^T, so every product needs the transpose of its right factor: one fused element-wise pass per step
 // writes a result and its transpose).  The backward pass walks the same chain in reverse with the stored H_k, Q_i.
-constexpr int kQrOrder = 10;
+constexpr int kQrOrder = 8;
 
 // out = ident * I + alpha * y (+ beta * y2), out_t = out^T; 32 x 32 tiles.  y2, out, out_t may be null.
 __global__ __launch_bounds__(256) void k_qr_combine(const float* __restrict__ y, const float* __restrict__ y2, float alpha, float beta,
