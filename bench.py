@@ -437,13 +437,13 @@ def bench_fold(torch, ae, args):
 
 
 # measured HBM bytes per product launch of the QR parametrisation (profiles/qr_param.md)
-QR_TRAFFIC_BYTES = {"f32": 8.59e8}
+QR_TRAFFIC_BYTES = {"f32": 8.56e8}
 
 
 def bench_qr_param(torch, ae, args):
     """One step = the QR parametrisation A = exp((G - G^T)/2)(R + diag s) of Eq. (5) for one d x d matrix, d = 4 096:
-    compose A (order-8 Taylor polynomial, five squarings), the volume regulariser, and the parameter gradients from
-    dLoss/dA through the stored chain: 13 + 26 dense binary32 products of 2 d^3 FLOPs each."""
+    compose A (order-8 Taylor polynomial in powers of X^3, five squarings), the volume regulariser, and the parameter
+    gradients from dLoss/dA through the stored chain: 10 + 20 dense binary32 products of 2 d^3 FLOPs each."""
     d, squarings = 4096, 5
     td = torch.bfloat16 if args.dtype == "bf16" else torch.float32
     params = wl.make_qr_params(d, seed=13, kind="bd_orthogonal", noise=1e-3)

@@ -263,7 +263,7 @@ int model_lu_timing(int enable, double* gemm_ms, int64_t* launches);
  *     Q = exp((G - G^T) / 2),   A = Q (R + diag(s)).
  * Free parameters (device, binary32 master copies): g [d][d] (only its skew-symmetric part acts), rp [d][d] of which
  * the strictly upper part is read, log_s, sign_s [d] as for the LU form.  The exponential is scaling and squaring
- * in binary32 on the matrix cores: X = S / 2^squarings, a Taylor polynomial of order 8 in Horner form, then
+ * in binary32 on the matrix cores: X = S / 2^squarings, the Taylor polynomial of order 8 (evaluated in powers of X^3), then
  * `squarings` squarings; choose squarings with 2^squarings >= 2 ||S||_2 (5 covers ||S|| <= 16; 0 .. 16 accepted).
  * d: a multiple of 32, 32..16384.  workspace: model_qr_workspace bytes ((16 + 2 squarings) d x d binary32 matrices),
  * 16-byte aligned like every [d][d] array.

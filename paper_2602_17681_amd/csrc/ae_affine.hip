@@ -459,10 +459,15 @@ int tri_inverse(const LuSrc& q, int dp, float* mneg, float* tt, float* x, float*
 }
 
 // ---- QR parametrisation (Eq. 5):  Q = exp((G - G^T) / 2),  A = Q (R + diag s) ------------------------------------
-// The exponential is scaling and squaring: X = S / 2^J, a Taylor polynomial of order M in Horner form
-// (H_M = I + X/M, H_k = I + X H_{k+1} / k), then J squarings — all binary32 products on the matrix cores
-// (y = x w^T, so every product needs the transpose of its right factor: one fused element-wise pass per step
-// writes a result and its transpose).  The backward pass walks the same chain in reverse with the stored H_k, Q_i.
+// The exponential is scaling and squaring: X = S / 2^J, the Taylor polynomial of order 8, then J squarings — all
+// binary32 products on the matrix cores.  The polynomial is evaluated in powers of Y = X^3 (four products instead of
+// the seven of Horner's rule in X):
+//     X2 = X X,  Y = X2 X,   B0 = I + X + X2/2,  B1 = I/3! + X/4! + X2/5!,  B2 = I/6! + X/7! + X2/8!,
+//     U = B1 + B2 Y,   Q_0 = B0 + U Y.
+// The product kernel computes y = x w^T; X is exactly skew-symmetric, so X^T = -X, X2^T = X2, Y^T = -Y and none of
+// these factors needs a transposed copy (x X = -(x X^T)).  The backward pass is the adjoint of this chain, step by
+// step, with the stored X, X2, Y, U, U^T, B2, B2^T and Q_i, Q_i^T (eight products for the polynomial, two per
+// squaring); one fused element-wise pass (k_qr_combine) forms sums, scalings and transposes.
 constexpr int kQrOrder = 8;
 
 // out = ident * I + alpha * y (+ beta * y2), out_t = out^T; 32 x 32 tiles.  y2, out, out_t may be null.
@@ -526,7 +531,14 @@ void qr_combine(const float* y, const float* y2, float alpha, float beta, float 
 struct QrSlots {
   float* base; int64_t dd; int J;
   float* x() const { return base; }                                  // S / 2^J
-  float* h(int k) const { return base + (int64_t)(k - 1) * dd; }     // H_k, k = 2 .. kQrOrder  (slots 1 .. kQrOrder-1)
+  float* h(int k) const { return base + (int64_t)(k - 1) * dd; }     // slots 1 .. kQrOrder-1 (k = 2 .. kQrOrder):
+  float* x2() const { return h(2); }                                 //   X X (symmetric)
+  float* y3() const { return h(3); }                                 //   X^3 (skew-symmetric)
+  float* u() const { return h(4); }                                  //   U = B1 + B2 Y
+  float* ut() const { return h(5); }
+  float* b2() const { return h(6); }                                 //   B2 = I/6! + X/7! + X2/8!
+  float* b2t() const { return h(7); }
+  float* spare() const { return h(8); }                              //   a seventh temporary of the backward pass
   float* q(int i) const { return base + (int64_t)(kQrOrder + i) * dd; }              // Q_i, i = 0 .. J
   float* qt(int i) const { return base + (int64_t)(kQrOrder + J + 1 + i) * dd; }     // Q_i^T
   float* tmp(int t) const { return base + (int64_t)(kQrOrder + 2 * (J + 1) + t) * dd; }   // six temporaries
@@ -656,17 +668,23 @@ extern "C" int model_qr_compose(const float* g, const float* rp, const float* lo
   const QrSlots w{reinterpret_cast<float*>(workspace), d * d, J};
   const dim3 tgrid(n / 32, n / 32);
   hipLaunchKernelGGL(k_qr_skew, tgrid, dim3(256), 0, s, g, 0.5f / (float)(1 << J), n, w.x());
-  float* ht = w.tmp(0);
   float* y = w.tmp(1);
-  qr_combine(w.x(), nullptr, 1.0f / kQrOrder, 0.0f, 1.0f, n, w.h(kQrOrder), ht, s);        // H_M = I + X / M
-  AE_TRY(launch_status("qr_first"));
-  for (int k = kQrOrder - 1; k >= 1; --k) {
-    AE_TRY(dense_product(w.x(), ht, y, n, AE_F32, CONV_TRI_NONE, s));                       // X H_{k+1}
-    float* hk = k >= 2 ? w.h(k) : w.q(0);
-    float* hkt = k >= 2 ? ht : w.qt(0);
-    qr_combine(y, nullptr, 1.0f / (float)k, 0.0f, 1.0f, n, hk, hkt, s);                     // H_k = I + X H_{k+1} / k
-    AE_TRY(launch_status("qr_horner"));
-  }
+  float* b = w.tmp(0);
+  // (dense_product(x, w, out) = x w^T; with w skew-symmetric that is -(x w))
+  AE_TRY(dense_product(w.x(), w.x(), y, n, AE_F32, CONV_TRI_NONE, s));                      // X X^T = -X2
+  qr_combine(y, nullptr, -1.0f, 0.0f, 0.0f, n, w.x2(), nullptr, s);
+  AE_TRY(dense_product(w.x2(), w.x(), y, n, AE_F32, CONV_TRI_NONE, s));                     // X2 X^T = -Y
+  qr_combine(y, nullptr, -1.0f, 0.0f, 0.0f, n, w.y3(), nullptr, s);
+  qr_combine(w.x(), w.x2(), 1.0f / 5040.0f, 1.0f / 40320.0f, 1.0f / 720.0f, n, w.b2(), w.b2t(), s);
+  AE_TRY(launch_status("qr_powers"));
+  AE_TRY(dense_product(w.b2(), w.y3(), y, n, AE_F32, CONV_TRI_NONE, s));                    // B2 Y^T = -B2 Y
+  qr_combine(w.x(), w.x2(), 1.0f / 24.0f, 1.0f / 120.0f, 1.0f / 6.0f, n, b, nullptr, s);    // B1
+  qr_combine(y, b, -1.0f, 1.0f, 0.0f, n, w.u(), w.ut(), s);                                 // U = B1 + B2 Y
+  AE_TRY(launch_status("qr_u"));
+  AE_TRY(dense_product(w.u(), w.y3(), y, n, AE_F32, CONV_TRI_NONE, s));                     // U Y^T = -U Y
+  qr_combine(w.x(), w.x2(), 1.0f, 0.5f, 1.0f, n, b, nullptr, s);                            // B0
+  qr_combine(y, b, -1.0f, 1.0f, 0.0f, n, w.q(0), w.qt(0), s);                               // Q_0 = B0 + U Y
+  AE_TRY(launch_status("qr_polynomial"));
   for (int i = 0; i < J; ++i) {
     AE_TRY(dense_product(w.q(i), w.qt(i), w.q(i + 1), n, AE_F32, CONV_TRI_NONE, s));        // Q_{i+1} = Q_i Q_i
     qr_combine(w.q(i + 1), nullptr, 1.0f, 0.0f, 0.0f, n, nullptr, w.qt(i + 1), s);
@@ -717,16 +735,35 @@ extern "C" int model_qr_backward(const void* g_a, const float* rp, const float* 
     qr_combine(t0, t1, 1.0f, 1.0f, 0.0f, n, cur, cur_t, s);
     AE_TRY(launch_status("qr_backward_square"));
   }
-  // Horner steps in reverse: cur = dH_k;  dX += dH_k H_{k+1}^T / k,  dH_{k+1} = X^T dH_k / k = -X dH_k / k
-  float* dx = t5;
-  for (int k = 1; k <= kQrOrder - 1; ++k) {
-    AE_TRY(dense_product(cur, w.h(k + 1), t0, n, AE_F32, CONV_TRI_NONE, s));
-    hipLaunchKernelGGL(k_qr_axpy, dim3(lu_grid(dd)), dim3(256), 0, s, dx, (const float*)t0, 1.0f / (float)k, k == 1 ? 1 : 0, dd);
-    AE_TRY(dense_product(w.x(), cur_t, t1, n, AE_F32, CONV_TRI_NONE, s));
-    qr_combine(t1, nullptr, -1.0f / (float)k, 0.0f, 0.0f, n, cur, cur_t, s);
-    AE_TRY(launch_status("qr_backward_horner"));
-  }
-  hipLaunchKernelGGL(k_qr_axpy, dim3(lu_grid(dd)), dim3(256), 0, s, dx, (const float*)cur, 1.0f / kQrOrder, 0, dd);   // H_M = I + X / M
+  // the polynomial in reverse; A = dQ_0, B = its transpose, C .. G free
+  float *A = cur, *B = cur_t, *C = t0, *D = t1, *E = t2, *F = w.spare(), *G = t5;
+  const dim3 eg(lu_grid(dd)), eb(256);
+  AE_TRY(dense_product(A, w.y3(), C, n, AE_F32, CONV_TRI_NONE, s));                         // dU = dQ_0 Y^T
+  qr_combine(C, nullptr, 1.0f, 0.0f, 0.0f, n, nullptr, D, s);                               // dU^T
+  AE_TRY(dense_product(w.ut(), B, E, n, AE_F32, CONV_TRI_NONE, s));                         // U^T dQ_0        (Q_0 = B0 + U Y)
+  AE_TRY(dense_product(w.b2t(), D, F, n, AE_F32, CONV_TRI_NONE, s));                        // B2^T dU         (U = B1 + B2 Y)
+  qr_combine(E, F, 1.0f, 1.0f, 0.0f, n, E, D, s);                                           // dY = their sum (E) and dY^T (D)
+  AE_TRY(launch_status("qr_backward_dy"));
+  AE_TRY(dense_product(C, w.y3(), F, n, AE_F32, CONV_TRI_NONE, s));                         // dB2 = dU Y^T
+  // dX  = dB0 + dB1/4! + dB2/7!  + ...,   dX2 = dB0/2 + dB1/5! + dB2/8! + ...   with dB0 = dQ_0, dB1 = dU
+  hipLaunchKernelGGL(k_qr_axpy, eg, eb, 0, s, G, (const float*)A, 1.0f, 1, dd);
+  hipLaunchKernelGGL(k_qr_axpy, eg, eb, 0, s, G, (const float*)C, 1.0f / 24.0f, 0, dd);
+  hipLaunchKernelGGL(k_qr_axpy, eg, eb, 0, s, G, (const float*)F, 1.0f / 5040.0f, 0, dd);
+  hipLaunchKernelGGL(k_qr_axpy, eg, eb, 0, s, B, (const float*)A, 0.5f, 1, dd);
+  hipLaunchKernelGGL(k_qr_axpy, eg, eb, 0, s, B, (const float*)C, 1.0f / 120.0f, 0, dd);
+  hipLaunchKernelGGL(k_qr_axpy, eg, eb, 0, s, B, (const float*)F, 1.0f / 40320.0f, 0, dd);
+  AE_TRY(launch_status("qr_backward_db"));
+  AE_TRY(dense_product(E, w.x(), A, n, AE_F32, CONV_TRI_NONE, s));                          // Y = X2 X:  dX2 += dY X^T
+  hipLaunchKernelGGL(k_qr_axpy, eg, eb, 0, s, B, (const float*)A, 1.0f, 0, dd);
+  AE_TRY(dense_product(w.x2(), D, C, n, AE_F32, CONV_TRI_NONE, s));                         //            dX  += X2^T dY = X2 dY
+  hipLaunchKernelGGL(k_qr_axpy, eg, eb, 0, s, G, (const float*)C, 1.0f, 0, dd);
+  qr_combine(B, nullptr, 1.0f, 0.0f, 0.0f, n, nullptr, F, s);                               // dX2^T
+  AE_TRY(launch_status("qr_backward_dx2"));
+  AE_TRY(dense_product(B, w.x(), A, n, AE_F32, CONV_TRI_NONE, s));                          // X2 = X X:  dX += dX2 X^T
+  hipLaunchKernelGGL(k_qr_axpy, eg, eb, 0, s, G, (const float*)A, 1.0f, 0, dd);
+  AE_TRY(dense_product(w.x(), F, C, n, AE_F32, CONV_TRI_NONE, s));                          //            dX += X^T dX2 = -(X dX2)
+  hipLaunchKernelGGL(k_qr_axpy, eg, eb, 0, s, G, (const float*)C, -1.0f, 0, dd);
+  float* dx = G;
   // X = (G - G^T) / (2 * 2^J):  dG = (dX - dX^T) / (2 * 2^J)
   hipLaunchKernelGGL(k_qr_skew, dim3(n / 32, n / 32), dim3(256), 0, s, (const float*)dx, 0.5f / (float)(1 << J), n, d_g);
   return launch_status("qr_backward");
