@@ -317,6 +317,38 @@ def bench_lu_param(torch, ae, args):
         e1.record()
         torch.cuda.synchronize()
         inv_ms = e0.elapsed_time(e1) / 10
+    # beside the step: the per-block transformations of a 32-block model (32 matrices of the head dimension 128):
+    # compose + gradients + inverse of all of them, the batched calls (three launches) against the full-size calls
+    # matrix by matrix
+    cnt, dh = 32, 128
+    sets = [wl.make_lu_params(dh, seed=100 + m, kind="bd_hadamard", noise=1e-3) for m in range(cnt)]
+    st = [torch.from_numpy(np.ascontiguousarray(np.stack([p[i] for p in sets]))).cuda() for i in range(5)]
+    gs = torch.randn((cnt, dh, dh), device="cuda").to(td)
+    sa, si = torch.empty((cnt, dh, dh), dtype=td, device="cuda"), torch.empty((cnt, dh, dh), dtype=td, device="cuda")
+    sl, su, ss = torch.empty((cnt, dh, dh), device="cuda"), torch.empty((cnt, dh, dh), device="cuda"), torch.empty((cnt, dh), device="cuda")
+    wsm = torch.empty(max(ae.model_lu_workspace(dh, ae.DTYPES[args.dtype]), ae.model_lu_inverse_workspace(dh)), dtype=torch.uint8, device="cuda")
+
+    def small_batched():
+        ae.model_lu_compose_batch(*st, cnt, dh, sa)
+        ae.model_lu_backward_batch(gs, *st, cnt, dh, sl, su, ss)
+        ae.model_lu_inverse_batch(*st, cnt, dh, si)
+
+    def small_looped():
+        for m in range(cnt):
+            pm = [t[m] for t in st]
+            ae.model_lu_compose(*pm, dh, sa[m], wsm)
+            ae.model_lu_backward(gs[m], *pm, dh, sl[m], su[m], ss[m], wsm)
+            ae.model_lu_inverse(*pm, dh, si[m], wsm)
+
+    small_ms = {}
+    for name, fn, reps in (("batched", small_batched, 20), ("looped_full_size", small_looped, 3)):
+        fn()
+        torch.cuda.synchronize()
+        c0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        small_ms[name] = (time.perf_counter() - c0) / reps * 1e3
     flops = 2.0 * d ** 3                     # 3 x (2/3) d^3
     ach = flops / 3.0 / avg_ms / 1e9
     es = a.element_size()
@@ -340,7 +372,8 @@ def bench_lu_param(torch, ae, args):
         "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": args.dtype, "data": "synthetic",
         "config": {"workload": "lu_param: A = P L (U + diag s), d = %d, block-Hadamard initialisation + noise" % d, "d": d,
-                   "inverse_ms_beside_the_step": inv_ms},
+                   "inverse_ms_beside_the_step": inv_ms,
+                   "per_block_matrices_32x128_compose_gradients_inverse_ms": small_ms},
         # the three GEMM launches of a step (62 % of its kernel time; twelve element-wise kernels are the rest)
         "roofline": {"bound": "mfma", "kernel": "k_igemm (triangular K ranges)", "achieved": ach, "peak": PEAK[args.dtype],
                      "unit": "TFLOP/s", "frac": ach / PEAK[args.dtype], "achieved_whole_step": flops / step_ms / 1e9,

@@ -253,6 +253,21 @@ int model_vol_penalty(const float* log_s, int64_t d, float* value, float* d_log_
 int model_lu_inverse_workspace(int64_t d, int64_t* bytes);
 int model_lu_inverse(const float* lp, const float* up, const float* log_s, const float* sign_s, const int* perm, int64_t d,
                      int dtype, void* a_inv_out, void* workspace, void* stream);
+/* The same three operations for MANY SMALL matrices in one launch each (the per-block transformations: one d x d
+ * parameter set per transformer block, d the head dimension): `count` independent parameter sets stored one after
+ * the other — lp, up [count][d][d], log_s, sign_s [count][d], perm [count][d] (each a permutation of 0..d-1) — and
+ * results laid out the same way (a_out, a_inv_out, g: [count][d][d] in dtype; d_lp, d_up [count][d][d], d_log_s
+ * [count][d] in binary32).  One workgroup owns one matrix, which lives in LDS; all arithmetic is binary32, only the
+ * stored a_out / a_inv_out (and the given g) are in dtype.  1 <= d <= 128 (larger matrices take the calls above),
+ * 1 <= count <= 2^20, no workspace, no alignment requirement beyond the element types'.  Same definitions, same
+ * treatment of perm and of zeros in s as model_lu_compose / model_lu_backward / model_lu_inverse. */
+int model_lu_compose_batch(const float* lp, const float* up, const float* log_s, const float* sign_s, const int* perm,
+                           int64_t count, int64_t d, int dtype, void* a_out, void* stream);
+int model_lu_backward_batch(const void* g, const float* lp, const float* up, const float* log_s, const float* sign_s,
+                            const int* perm, int64_t count, int64_t d, int dtype, float* d_lp, float* d_up,
+                            float* d_log_s, void* stream);
+int model_lu_inverse_batch(const float* lp, const float* up, const float* log_s, const float* sign_s, const int* perm,
+                           int64_t count, int64_t d, int dtype, void* a_inv_out, void* stream);
 /* Measurement aid (not thread safe): returns in *gemm_ms / *launches (host, nullable) the time and count of the
  * matrix-core products model_lu_compose / model_lu_backward launched since the last call, then clears both and
  * switches the timing on (enable != 0) or off.  While it is on, every product is bracketed by HIP events on its

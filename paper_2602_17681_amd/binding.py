@@ -23,7 +23,7 @@ SYMBOLS = [
     "model_set_sample_offset", "model_forward", "model_backward", "model_loss_mse", "model_noise",
     "model_pnorm_awgn", "model_gen_bits", "model_count_errors", "model_num_steps", "model_step_info",
     "model_get_activation", "model_timing_enable", "model_set_overlap", "model_calibrate_mfma", "model_mx_quantize", "model_mx_quantize_elem", "model_transform_mse_workspace",
-    "model_transform_mse", "model_transform_mse_elem", "model_lu_workspace", "model_lu_compose", "model_lu_backward", "model_vol_penalty", "model_lu_inverse_workspace", "model_lu_inverse", "model_lu_timing", "model_qr_workspace", "model_qr_compose", "model_qr_backward", "model_qr_inverse", "model_fold_workspace", "model_fold_linear", "model_fold_embedding", "model_timing_slots",
+    "model_transform_mse", "model_transform_mse_elem", "model_lu_workspace", "model_lu_compose", "model_lu_backward", "model_vol_penalty", "model_lu_inverse_workspace", "model_lu_inverse", "model_lu_compose_batch", "model_lu_backward_batch", "model_lu_inverse_batch", "model_lu_timing", "model_qr_workspace", "model_qr_compose", "model_qr_backward", "model_qr_inverse", "model_fold_workspace", "model_fold_linear", "model_fold_embedding", "model_timing_slots",
     "model_timing_read", "model_timing_reset", "model_last_error",
 ]
 
@@ -72,6 +72,9 @@ def _load():
     L.model_lu_timing.argtypes = [C.c_int, C.POINTER(C.c_double), i64p]
     L.model_lu_inverse_workspace.argtypes = [C.c_int64, i64p]
     L.model_lu_inverse.argtypes = [vp, vp, vp, vp, vp, C.c_int64, C.c_int, vp, vp, vp]
+    L.model_lu_compose_batch.argtypes = [vp, vp, vp, vp, vp, C.c_int64, C.c_int64, C.c_int, vp, vp]
+    L.model_lu_backward_batch.argtypes = [vp, vp, vp, vp, vp, vp, C.c_int64, C.c_int64, C.c_int, vp, vp, vp, vp]
+    L.model_lu_inverse_batch.argtypes = [vp, vp, vp, vp, vp, C.c_int64, C.c_int64, C.c_int, vp, vp]
     L.model_qr_workspace.argtypes = [C.c_int64, C.c_int, i64p]
     L.model_qr_compose.argtypes = [vp, vp, vp, vp, C.c_int64, C.c_int, C.c_int, vp, vp, vp]
     L.model_qr_backward.argtypes = [vp, vp, vp, vp, C.c_int64, C.c_int, C.c_int, vp, vp, vp, vp, vp]
@@ -303,6 +306,32 @@ def model_lu_inverse(lp, up, log_s, sign_s, perm, d, a_inv_out, workspace):
     dtype = AE_BF16 if a_inv_out.dtype == torch.bfloat16 else AE_F32
     assert a_inv_out.numel() == d * d and workspace.numel() * workspace.element_size() >= model_lu_inverse_workspace(d)
     _check(lib.model_lu_inverse(*_lu_params(lp, up, log_s, sign_s, perm, d), d, dtype, _ptr(a_inv_out), _ptr(workspace), _stream()))
+
+
+def _lu_batch_params(lp, up, log_s, sign_s, perm, count, d):
+    assert lp.numel() == count * d * d and up.numel() == count * d * d
+    assert log_s.numel() == count * d and sign_s.numel() == count * d and perm.numel() == count * d
+    return (_ptr(lp, torch.float32), _ptr(up, torch.float32), _ptr(log_s, torch.float32), _ptr(sign_s, torch.float32),
+            _ptr(perm, torch.int32))
+
+
+def model_lu_compose_batch(lp, up, log_s, sign_s, perm, count, d, a_out):
+    dtype = AE_BF16 if a_out.dtype == torch.bfloat16 else AE_F32
+    assert a_out.numel() == count * d * d
+    _check(lib.model_lu_compose_batch(*_lu_batch_params(lp, up, log_s, sign_s, perm, count, d), count, d, dtype, _ptr(a_out), _stream()))
+
+
+def model_lu_backward_batch(g, lp, up, log_s, sign_s, perm, count, d, d_lp, d_up, d_log_s):
+    dtype = AE_BF16 if g.dtype == torch.bfloat16 else AE_F32
+    assert g.numel() == count * d * d and d_lp.numel() == count * d * d and d_up.numel() == count * d * d and d_log_s.numel() == count * d
+    _check(lib.model_lu_backward_batch(_ptr(g), *_lu_batch_params(lp, up, log_s, sign_s, perm, count, d), count, d, dtype,
+                                       _ptr(d_lp, torch.float32), _ptr(d_up, torch.float32), _ptr(d_log_s, torch.float32), _stream()))
+
+
+def model_lu_inverse_batch(lp, up, log_s, sign_s, perm, count, d, a_inv_out):
+    dtype = AE_BF16 if a_inv_out.dtype == torch.bfloat16 else AE_F32
+    assert a_inv_out.numel() == count * d * d
+    _check(lib.model_lu_inverse_batch(*_lu_batch_params(lp, up, log_s, sign_s, perm, count, d), count, d, dtype, _ptr(a_inv_out), _stream()))
 
 
 def model_vol_penalty(log_s, d, value, d_log_s=None):

@@ -254,22 +254,11 @@ __global__ __launch_bounds__(256) void k_tri_prepare(LuSrc q, int dp, float* __r
   }
 }
 
-// X_bb = M_bb^-1 for every 128 x 128 diagonal block b (one workgroup of 256 threads each), the same recursion inside
-// LDS: 16 x 16 diagonal blocks by forward substitution (thread j solves column j of its block), then three levels
-// of merges [[X11, 0], [-X22 M21 X11, X22]] with all threads sharing the outputs of the two small products.  The
-// block and its transpose are written into the full matrices x and xt.
-template <int WHICH>
-__global__ __launch_bounds__(256) void k_tri_diag_inverse(LuSrc q, int dp, float* __restrict__ x, float* __restrict__ xt) {
-  __shared__ float mb[128][129];
-  __shared__ float xb[128][129];
-  __shared__ float tb[64 * 64];                        // M21 X11 of every pair of the current level: pairs * b * b = 64 b values
-  const int blk = blockIdx.x, tid = threadIdx.x, o = blk * 128;
-  for (int e = tid; e < 128 * 128; e += 256) {
-    const int i = e >> 7, j = e & 127;
-    mb[i][j] = tri_elem<WHICH>(q, o + i, o + j);
-    xb[i][j] = 0.0f;
-  }
-  __syncthreads();
+// xb = mb^-1 for a lower triangular 128 x 128 matrix in LDS (all 256 threads of the workgroup; xb must be zero on
+// entry and both arrays visible to every thread; ends on a barrier): 16 x 16 diagonal blocks by forward substitution
+// (thread j solves column j of its block), then three levels of merges [[X11, 0], [-X22 M21 X11, X22]] with all
+// threads sharing the outputs of the two small products.  tb: 64 * 64 values of scratch.
+__device__ __forceinline__ void tri128_inverse_lds(float (*mb)[129], float (*xb)[129], float* tb, int tid) {
   if (tid < 128) {                                     // column tid of its 16 x 16 diagonal block
     const int j = tid, b0 = j & ~15;
     for (int i = j; i < b0 + 16; ++i) {
@@ -281,7 +270,7 @@ __global__ __launch_bounds__(256) void k_tri_diag_inverse(LuSrc q, int dp, float
   __syncthreads();
   for (int b = 16; b < 128; b *= 2) {
     const int lb = b == 16 ? 4 : (b == 32 ? 5 : 6);    // log2 b
-    // T[p][r][c] = sum_k M21[r][k] X11[k][c], X11 lower triangular: k >= c
+    // T[p][r][c] = sum_k M21[r][k] X11[k][c], X11 lower triangular: k >= c   (pairs * b * b = 64 b values)
     for (int e = tid; e < 64 * b; e += 256) {
       const int p = e >> (2 * lb), r = (e >> lb) & (b - 1), c = e & (b - 1);
       const int r1 = (2 * p + 1) * b + r, c0 = 2 * p * b;
@@ -311,11 +300,221 @@ __global__ __launch_bounds__(256) void k_tri_diag_inverse(LuSrc q, int dp, float
     }
     __syncthreads();
   }
+}
+
+// X_bb = M_bb^-1 for every 128 x 128 diagonal block b (one workgroup of 256 threads each) by the recursion above;
+// the block and its transpose are written into the full matrices x and xt.
+template <int WHICH>
+__global__ __launch_bounds__(256) void k_tri_diag_inverse(LuSrc q, int dp, float* __restrict__ x, float* __restrict__ xt) {
+  __shared__ float mb[128][129];
+  __shared__ float xb[128][129];
+  __shared__ float tb[64 * 64];
+  const int blk = blockIdx.x, tid = threadIdx.x, o = blk * 128;
+  for (int e = tid; e < 128 * 128; e += 256) {
+    const int i = e >> 7, j = e & 127;
+    mb[i][j] = tri_elem<WHICH>(q, o + i, o + j);
+    xb[i][j] = 0.0f;
+  }
+  __syncthreads();
+  tri128_inverse_lds(mb, xb, tb, tid);
   for (int e = tid; e < 128 * 128; e += 256) {
     const int i = e >> 7, j = e & 127;
     x[(int64_t)(o + i) * dp + o + j] = xb[i][j];
     xt[(int64_t)(o + i) * dp + o + j] = xb[j][i];
   }
+}
+
+// ---- many small matrices at once (the per-block transformations: one d x d parameter set per transformer block, d the
+// head dimension) --------------------------------------------------------------------------------------------------
+// For d <= 128 a matrix fits into LDS, and the full-size path above would be a dozen launch-bound kernels per matrix.
+// Here one workgroup of 256 threads owns one matrix and one launch covers `count` of them; the products are plain
+// binary32 multiply-adds out of LDS (2 d^3 operations per product: microseconds).  Thread (ty, tx) = (tid / 16,
+// tid % 16) owns the outputs (ty + 16 a, tx + 16 b), a, b = 0..7.
+__device__ __forceinline__ LuSrc small_src(const float* lp, const float* up, const float* log_s, const float* sign_s, int d, int m) {
+  const int64_t mo = (int64_t)m * d * d, vo = (int64_t)m * d;
+  return LuSrc{lp + mo, up + mo, log_s + vo, sign_s + vo, nullptr, nullptr, d};
+}
+__device__ __forceinline__ int small_perm(const int* perm, int d, int i) {       // an entry out of range is treated as i
+  const int p = perm[i];
+  return (unsigned)p < (unsigned)d ? p : i;
+}
+
+// out[r][j] = sum_k L[perm[r]][k] (U + diag s)[k][j]
+template <typename T>
+__global__ __launch_bounds__(256) void k_lu_small_compose(const float* __restrict__ lp, const float* __restrict__ up, const float* __restrict__ log_s,
+                                                          const float* __restrict__ sign_s, const int* __restrict__ perm, int d, T* __restrict__ out) {
+  __shared__ float lm[128][129];
+  __shared__ float um[128][129];
+  const int m = blockIdx.x, tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
+  const LuSrc q = small_src(lp, up, log_s, sign_s, d, m);
+  for (int e = tid; e < d * d; e += 256) {
+    const int i = e / d, j = e - i * d;
+    lm[i][j] = tri_elem<0>(q, i, j);
+    um[j][i] = tri_elem<1>(q, i, j);                   // tri_elem<1> is (U + diag s)^T
+  }
+  __syncthreads();
+  int pr[8];
+#pragma unroll
+  for (int a = 0; a < 8; ++a) pr[a] = ty + 16 * a < d ? small_perm(perm + (int64_t)m * d, d, ty + 16 * a) : 0;
+  float acc[8][8];
+#pragma unroll
+  for (int a = 0; a < 8; ++a)
+#pragma unroll
+    for (int b = 0; b < 8; ++b) acc[a][b] = 0.0f;
+  for (int k = 0; k < d; ++k) {
+    float av[8], bv[8];
+#pragma unroll
+    for (int a = 0; a < 8; ++a) av[a] = ty + 16 * a < d ? lm[pr[a]][k] : 0.0f;
+#pragma unroll
+    for (int b = 0; b < 8; ++b) bv[b] = tx + 16 * b < d ? um[k][tx + 16 * b] : 0.0f;
+#pragma unroll
+    for (int a = 0; a < 8; ++a)
+#pragma unroll
+      for (int b = 0; b < 8; ++b) acc[a][b] = fmaf(av[a], bv[b], acc[a][b]);
+  }
+  T* o = out + (int64_t)m * d * d;
+#pragma unroll
+  for (int a = 0; a < 8; ++a)
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+      const int r = ty + 16 * a, j = tx + 16 * b;
+      if (r < d && j < d) Store<T>::st(o + (int64_t)r * d + j, acc[a][b]);
+    }
+}
+
+// B = P^T G (B[perm[i]] = G[i]);  d_up = strictly upper part of L^T B, d_log_s = its diagonal times s,
+// d_lp = strictly lower part of B (U + diag s)^T
+template <typename T>
+__global__ __launch_bounds__(256) void k_lu_small_backward(const T* __restrict__ g, const float* __restrict__ lp, const float* __restrict__ up,
+                                                           const float* __restrict__ log_s, const float* __restrict__ sign_s, const int* __restrict__ perm,
+                                                           int d, float* __restrict__ d_lp, float* __restrict__ d_up, float* __restrict__ d_log_s) {
+  __shared__ float bm[128][129];
+  __shared__ float fm[128][129];
+  const int m = blockIdx.x, tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
+  const int64_t mo = (int64_t)m * d * d, vo = (int64_t)m * d;
+  const LuSrc q = small_src(lp, up, log_s, sign_s, d, m);
+  for (int e = tid; e < d * d; e += 256) {
+    const int i = e / d, j = e - i * d;
+    bm[i][j] = 0.0f;                                   // (rows that a perm with duplicates never names)
+    fm[i][j] = tri_elem<0>(q, i, j);
+  }
+  __syncthreads();
+  for (int e = tid; e < d * d; e += 256) {
+    const int i = e / d, j = e - i * d;
+    bm[small_perm(perm + vo, d, i)][j] = Store<T>::ld(g + mo + e);
+  }
+  __syncthreads();
+  float acc[8][8];
+#pragma unroll
+  for (int a = 0; a < 8; ++a)
+#pragma unroll
+    for (int b = 0; b < 8; ++b) acc[a][b] = 0.0f;
+  for (int i = 0; i < d; ++i) {                        // (L^T B)[k][n] = sum_i L[i][k] B[i][n]
+    float av[8], bv[8];
+#pragma unroll
+    for (int a = 0; a < 8; ++a) av[a] = ty + 16 * a < d ? fm[i][ty + 16 * a] : 0.0f;
+#pragma unroll
+    for (int b = 0; b < 8; ++b) bv[b] = tx + 16 * b < d ? bm[i][tx + 16 * b] : 0.0f;
+#pragma unroll
+    for (int a = 0; a < 8; ++a)
+#pragma unroll
+      for (int b = 0; b < 8; ++b) acc[a][b] = fmaf(av[a], bv[b], acc[a][b]);
+  }
+#pragma unroll
+  for (int a = 0; a < 8; ++a)
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+      const int k = ty + 16 * a, n = tx + 16 * b;
+      if (k < d && n < d) {
+        d_up[mo + (int64_t)k * d + n] = n > k ? acc[a][b] : 0.0f;
+        if (n == k) d_log_s[vo + k] = acc[a][b] * (q.sign[k] * expf(q.log_s[k]));
+      }
+      acc[a][b] = 0.0f;
+    }
+  __syncthreads();
+  for (int e = tid; e < d * d; e += 256) {
+    const int i = e / d, j = e - i * d;
+    fm[j][i] = tri_elem<1>(q, i, j);                   // fm = U + diag s
+  }
+  __syncthreads();
+  for (int n = 0; n < d; ++n) {                        // (B (U + diag s)^T)[r][k] = sum_n B[r][n] (U + diag s)[k][n]
+    float av[8], bv[8];
+#pragma unroll
+    for (int a = 0; a < 8; ++a) av[a] = ty + 16 * a < d ? bm[ty + 16 * a][n] : 0.0f;
+#pragma unroll
+    for (int b = 0; b < 8; ++b) bv[b] = tx + 16 * b < d ? fm[tx + 16 * b][n] : 0.0f;
+#pragma unroll
+    for (int a = 0; a < 8; ++a)
+#pragma unroll
+      for (int b = 0; b < 8; ++b) acc[a][b] = fmaf(av[a], bv[b], acc[a][b]);
+  }
+#pragma unroll
+  for (int a = 0; a < 8; ++a)
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+      const int r = ty + 16 * a, k = tx + 16 * b;
+      if (r < d && k < d) d_lp[mo + (int64_t)r * d + k] = k < r ? acc[a][b] : 0.0f;
+    }
+}
+
+// out[i][c] = ((U + diag s)^-1 L^-1)[i][perm[c]]: both factors inverted by the in-LDS recursion (padded to 128 with an
+// identity block), L^-1 parked in registers while (U + diag s)^T is inverted
+template <typename T>
+__global__ __launch_bounds__(256) void k_lu_small_inverse(const float* __restrict__ lp, const float* __restrict__ up, const float* __restrict__ log_s,
+                                                          const float* __restrict__ sign_s, const int* __restrict__ perm, int d, T* __restrict__ out) {
+  __shared__ float mb[128][129];
+  __shared__ float xb[128][129];
+  __shared__ float tb[64 * 64];
+  const int m = blockIdx.x, tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
+  const LuSrc q = small_src(lp, up, log_s, sign_s, d, m);
+  for (int e = tid; e < 128 * 128; e += 256) {
+    const int i = e >> 7, j = e & 127;
+    mb[i][j] = tri_elem<0>(q, i, j);
+    xb[i][j] = 0.0f;
+  }
+  __syncthreads();
+  tri128_inverse_lds(mb, xb, tb, tid);
+  float keep[64];                                      // L^-1, element tid + 256 e
+#pragma unroll
+  for (int e = 0; e < 64; ++e) keep[e] = xb[(tid + 256 * e) >> 7][(tid + 256 * e) & 127];
+  __syncthreads();
+  for (int e = tid; e < 128 * 128; e += 256) {
+    const int i = e >> 7, j = e & 127;
+    mb[i][j] = tri_elem<1>(q, i, j);
+    xb[i][j] = 0.0f;
+  }
+  __syncthreads();
+  tri128_inverse_lds(mb, xb, tb, tid);                 // xb = ((U + diag s)^T)^-1 = ((U + diag s)^-1)^T
+#pragma unroll
+  for (int e = 0; e < 64; ++e) mb[(tid + 256 * e) >> 7][(tid + 256 * e) & 127] = keep[e];
+  __syncthreads();
+  int pc[8];
+#pragma unroll
+  for (int b = 0; b < 8; ++b) pc[b] = tx + 16 * b < d ? small_perm(perm + (int64_t)m * d, d, tx + 16 * b) : 0;
+  float acc[8][8];
+#pragma unroll
+  for (int a = 0; a < 8; ++a)
+#pragma unroll
+    for (int b = 0; b < 8; ++b) acc[a][b] = 0.0f;
+  for (int k = 0; k < d; ++k) {                        // sum_k (U + diag s)^-1[i][k] L^-1[k][j]
+    float av[8], bv[8];
+#pragma unroll
+    for (int a = 0; a < 8; ++a) av[a] = xb[k][ty + 16 * a];
+#pragma unroll
+    for (int b = 0; b < 8; ++b) bv[b] = mb[k][pc[b]];
+#pragma unroll
+    for (int a = 0; a < 8; ++a)
+#pragma unroll
+      for (int b = 0; b < 8; ++b) acc[a][b] = fmaf(av[a], bv[b], acc[a][b]);
+  }
+  T* o = out + (int64_t)m * d * d;
+#pragma unroll
+  for (int a = 0; a < 8; ++a)
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+      const int i = ty + 16 * a, c = tx + 16 * b;
+      if (i < d && c < d) Store<T>::st(o + (int64_t)i * d + c, acc[a][b]);
+    }
 }
 
 // out[r][c] = z[r][perm[c]] in the storage type (z P^T); z has rows of dp entries, out is d x d
@@ -558,8 +757,49 @@ int check_lu_size(const char* who, int64_t d, int dtype) {
   return AE_OK;
 }
 
+int check_small_batch(const char* who, int64_t count, int64_t d, int dtype) {
+  if (dtype != AE_F32 && dtype != AE_BF16) return fail(AE_EINVAL, "%s: bad dtype", who);
+  if (d < 1 || d > 128) return fail(AE_EINVAL, "%s: d must be 1 .. 128 (larger matrices take the full-size calls)", who);
+  if (count < 1 || count > (1 << 20)) return fail(AE_EINVAL, "%s: count must be 1 .. 2^20", who);
+  return AE_OK;
+}
+
 }  // namespace
 }  // namespace ae
+
+extern "C" int model_lu_compose_batch(const float* lp, const float* up, const float* log_s, const float* sign_s, const int* perm,
+                                      int64_t count, int64_t d, int dtype, void* a_out, void* stream) {
+  using namespace ae;
+  if (!lp || !up || !log_s || !sign_s || !perm || !a_out) return fail(AE_EINVAL, "model_lu_compose_batch: null argument");
+  AE_TRY(check_small_batch("model_lu_compose_batch", count, d, dtype));
+  hipStream_t s = (hipStream_t)stream;
+  if (dtype == AE_BF16) hipLaunchKernelGGL((k_lu_small_compose<bf16_t>), dim3((unsigned)count), dim3(256), 0, s, lp, up, log_s, sign_s, perm, (int)d, (bf16_t*)a_out);
+  else hipLaunchKernelGGL((k_lu_small_compose<float>), dim3((unsigned)count), dim3(256), 0, s, lp, up, log_s, sign_s, perm, (int)d, (float*)a_out);
+  return launch_status("lu_small_compose");
+}
+
+extern "C" int model_lu_backward_batch(const void* g, const float* lp, const float* up, const float* log_s, const float* sign_s,
+                                       const int* perm, int64_t count, int64_t d, int dtype, float* d_lp, float* d_up,
+                                       float* d_log_s, void* stream) {
+  using namespace ae;
+  if (!g || !lp || !up || !log_s || !sign_s || !perm || !d_lp || !d_up || !d_log_s) return fail(AE_EINVAL, "model_lu_backward_batch: null argument");
+  AE_TRY(check_small_batch("model_lu_backward_batch", count, d, dtype));
+  hipStream_t s = (hipStream_t)stream;
+  if (dtype == AE_BF16) hipLaunchKernelGGL((k_lu_small_backward<bf16_t>), dim3((unsigned)count), dim3(256), 0, s, (const bf16_t*)g, lp, up, log_s, sign_s, perm, (int)d, d_lp, d_up, d_log_s);
+  else hipLaunchKernelGGL((k_lu_small_backward<float>), dim3((unsigned)count), dim3(256), 0, s, (const float*)g, lp, up, log_s, sign_s, perm, (int)d, d_lp, d_up, d_log_s);
+  return launch_status("lu_small_backward");
+}
+
+extern "C" int model_lu_inverse_batch(const float* lp, const float* up, const float* log_s, const float* sign_s, const int* perm,
+                                      int64_t count, int64_t d, int dtype, void* a_inv_out, void* stream) {
+  using namespace ae;
+  if (!lp || !up || !log_s || !sign_s || !perm || !a_inv_out) return fail(AE_EINVAL, "model_lu_inverse_batch: null argument");
+  AE_TRY(check_small_batch("model_lu_inverse_batch", count, d, dtype));
+  hipStream_t s = (hipStream_t)stream;
+  if (dtype == AE_BF16) hipLaunchKernelGGL((k_lu_small_inverse<bf16_t>), dim3((unsigned)count), dim3(256), 0, s, lp, up, log_s, sign_s, perm, (int)d, (bf16_t*)a_inv_out);
+  else hipLaunchKernelGGL((k_lu_small_inverse<float>), dim3((unsigned)count), dim3(256), 0, s, lp, up, log_s, sign_s, perm, (int)d, (float*)a_inv_out);
+  return launch_status("lu_small_inverse");
+}
 
 extern "C" int model_lu_workspace(int64_t d, int dtype, int64_t* bytes) {
   using namespace ae;

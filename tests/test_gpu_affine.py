@@ -398,3 +398,71 @@ def test_qr_argument_checks(ae):
     assert ae.lib.model_qr_compose(p, p, p, p, 64, 0, -1, p, p, None) == -1
     assert ae.lib.model_qr_compose(None, p, p, p, 64, 0, 5, p, p, None) == -1
     assert ae.lib.model_qr_backward(p, p, p, p, 64, 9, 5, p, p, p, p, None) == -1
+
+
+# ------------------------------------------------------------------ many small matrices in one launch (the per-block transformations)
+def _small_sets(count, d, seed, kind="random"):
+    sets = [wl.make_lu_params(d, seed=seed + 31 * m, kind=kind, noise=1e-3 if kind == "bd_hadamard" else 0.0,
+                              block=min(32, d)) for m in range(count)]
+    return sets, [np.stack([s[i] for s in sets]) for i in range(5)]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("count,d,kind", [(1, 128, "random"), (33, 128, "bd_hadamard"), (5, 64, "random"), (7, 96, "random"),
+                                          (3, 20, "random"), (4, 1, "random"), (300, 32, "bd_hadamard")])
+def test_small_batch_matches_oracle_matrix_by_matrix(ae, count, d, kind, dtype):
+    """model_lu_{compose,backward,inverse}_batch against the oracle applied to each parameter set on its own
+    (and numpy's inverse of the oracle's A); sizes below, at and not a divisor of the 128 x 128 LDS tile."""
+    import torch
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    sets, stacked = _small_sets(count, d, seed=1000 + count + d, kind=kind)
+    dev = [torch.from_numpy(np.ascontiguousarray(a)).cuda() for a in stacked]
+    rng = np.random.default_rng(count * 131 + d)
+    g = _round(rng.standard_normal((count, d, d)), dtype).astype(np.float64)
+    gt = torch.from_numpy(g.astype(np.float32)).cuda().to(td).contiguous()
+    a = torch.full((count, d, d), float("nan"), dtype=td, device="cuda")
+    ainv = torch.full((count, d, d), float("nan"), dtype=td, device="cuda")
+    dlp = torch.full((count, d, d), float("nan"), device="cuda")
+    dup = torch.full((count, d, d), float("nan"), device="cuda")
+    dls = torch.full((count, d), float("nan"), device="cuda")
+    ae.model_lu_compose_batch(*dev, count, d, a)
+    ae.model_lu_backward_batch(gt, *dev, count, d, dlp, dup, dls)
+    ae.model_lu_inverse_batch(*dev, count, d, ainv)
+    torch.cuda.synchronize()
+    a, ainv = a.float().cpu().numpy().astype(np.float64), ainv.float().cpu().numpy().astype(np.float64)
+    dlp, dup, dls = [t.cpu().numpy().astype(np.float64) for t in (dlp, dup, dls)]
+    for m, p in enumerate(sets):
+        a_ref = ao.lu_compose(*p)
+        assert _close(a[m], a_ref, TOL[dtype]), (m, np.abs(a[m] - a_ref).max())
+        r_lp, r_up, r_ls = ao.lu_gradients(g[m], *p)
+        assert _close(dlp[m], r_lp, TOL["f32"]) and _close(dup[m], r_up, TOL["f32"]) and _close(dls[m], r_ls, TOL["f32"]), m
+        assert np.all(np.triu(dlp[m]) == 0.0) and np.all(np.tril(dup[m]) == 0.0)
+        assert _close(ainv[m], np.linalg.inv(a_ref), TOL[dtype]), (m, np.abs(ainv[m] - np.linalg.inv(a_ref)).max())
+
+
+def test_small_batch_agrees_with_the_full_size_calls(ae):
+    """d = 128 is served by both paths: same A and A^-1 to binary32 rounding."""
+    d, count = 128, 3
+    sets, stacked = _small_sets(count, d, seed=77)
+    import torch
+    dev = [torch.from_numpy(np.ascontiguousarray(a)).cuda() for a in stacked]
+    a = torch.empty((count, d, d), device="cuda")
+    ainv = torch.empty((count, d, d), device="cuda")
+    ae.model_lu_compose_batch(*dev, count, d, a)
+    ae.model_lu_inverse_batch(*dev, count, d, ainv)
+    torch.cuda.synchronize()
+    for m, p in enumerate(sets):
+        assert _close(a[m].cpu().numpy().astype(np.float64), _compose(ae, p, d, "f32"), 1e-5)
+        assert _close(ainv[m].cpu().numpy().astype(np.float64), _inverse(ae, p, d, "f32"), 1e-4)
+
+
+def test_small_batch_argument_checks(ae):
+    import torch
+    t = torch.zeros(128 * 128, device="cuda")
+    p = C.c_void_p(t.data_ptr())
+    assert ae.lib.model_lu_compose_batch(p, p, p, p, p, 1, 129, 0, p, None) == -1 and "1 .. 128" in ae.model_last_error()
+    assert ae.lib.model_lu_compose_batch(p, p, p, p, p, 0, 64, 0, p, None) == -1
+    assert ae.lib.model_lu_compose_batch(p, p, p, p, p, 1, 64, 2, p, None) == -1
+    assert ae.lib.model_lu_compose_batch(None, p, p, p, p, 1, 64, 0, p, None) == -1
+    assert ae.lib.model_lu_backward_batch(p, p, p, p, p, p, 1, 0, 0, p, p, p, None) == -1
+    assert ae.lib.model_lu_inverse_batch(p, p, p, p, None, 1, 64, 0, p, None) == -1
