@@ -243,7 +243,7 @@ int model_lu_backward(const void* g, const float* lp, const float* up, const flo
 int model_vol_penalty(const float* log_s, int64_t d, float* value, float* d_log_s, void* stream);
 /* The inverse of the parametrised matrix, A^-1 = (U + diag s)^-1 L^-1 P^T (what the transformation error and the
  * folding take beside A): a_inv_out [d][d] in dtype.  Both triangular factors are inverted by a blocked recursion
- * (128 x 128 diagonal blocks by substitution, then neighbouring blocks merged, three launches per level), all in
+ * (128 x 128 diagonal blocks by substitution, then neighbouring blocks merged, two products and a transposing copy per level), all in
  * binary32 on the matrix cores; s must not contain zeros.  d: a multiple of 128, at most 16384.  The recursion works
  * at dp = 128 times the smallest power of two that reaches d, on the factors extended by an identity block (pairs,
  * tiles and K ranges wholly inside the padding are skipped); the last product and the output are d x d again.

@@ -224,9 +224,9 @@ void launch_build(const LuSrc& q, void* out, hipStream_t s) {
 // then neighbouring inverses X11, X22 of blocks of size b merge into the inverse of the 2b x 2b block,
 //     [[X11, 0], [-X22 M21 X11, X22]].
 // X and X^T live as full d x d binary32 matrices that start block diagonal and fill level by level; one level is
-// three launches of the matrix-core kernel over ALL pairs at once (K-range modes CONV_TRI_PAIR_*):
+// two launches of the matrix-core kernel over ALL pairs at once (K-range modes CONV_TRI_PAIR_*) and a transposing copy:
 //     T' = -(M21 X11)^T  into the upper blocks of a scratch matrix,   X21 = X22 T'^T  in place into X,
-//     X21^T = T' X22^T  in place into X^T.
+//     X21^T  into X^T.
 
 // entry (r, c) of the lower triangular matrix: WHICH 0: L; 1: (U + diag s)^T.  Rows and columns past d belong to
 // the identity block that pads the matrix to the working size of the recursion.
@@ -624,6 +624,19 @@ unsigned lu_grid(int64_t items) {
   return (unsigned)(g < 4096 ? (g < 1 ? 1 : g) : 4096);
 }
 
+// xt[c][r] = x[r][c] over the lower off-diagonal block (rows in block 2p+1, columns in block 2p, blocks of b) of every
+// pair p = blockIdx.z: 32 x 32 tiles through LDS
+__global__ __launch_bounds__(256) void k_tri_pair_transpose(const float* __restrict__ x, float* __restrict__ xt, int dp, int b) {
+  __shared__ float tile[32][33];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  const int r0 = (2 * (int)blockIdx.z + 1) * b + (int)blockIdx.y * 32, c0 = 2 * (int)blockIdx.z * b + (int)blockIdx.x * 32;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) tile[ty + 8 * j][tx] = x[(int64_t)(r0 + ty + 8 * j) * dp + c0 + tx];
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < 4; ++j) xt[(int64_t)(c0 + ty + 8 * j) * dp + r0 + tx] = tile[tx][ty + 8 * j];
+}
+
 // 128 times the smallest power of two that reaches d: the working size of the recursion
 int64_t tri_padded_size(int64_t d) {
   int64_t dp = 128;
@@ -651,8 +664,9 @@ int tri_inverse(const LuSrc& q, int dp, float* mneg, float* tt, float* x, float*
     AE_TRY(launch_conv_mfma(a, s));
     a.x = x; a.w = tt; a.y = x; a.tri = CONV_TRI_PAIR_LOWER_K1;           // X21 = X22 T'^T (reads the diagonal blocks of x, writes below them)
     AE_TRY(launch_conv_mfma(a, s));
-    a.x = tt; a.w = x; a.y = xt; a.tri = CONV_TRI_PAIR_UPPER_K1;          // X21^T = T' X22^T
-    AE_TRY(launch_conv_mfma(a, s));
+    // X21^T into X^T: a transposing copy (a third product would give the same block at fifteen times the cost)
+    hipLaunchKernelGGL(k_tri_pair_transpose, dim3(b / 32, b / 32, a.tri_pairs), dim3(256), 0, s, (const float*)x, xt, d, b);
+    AE_TRY(launch_status("tri_pair_transpose"));
   }
   return AE_OK;
 }

@@ -65,9 +65,9 @@ struct IgemmParams {
   //   4: x[m][k] = 0 for k < m and w[n][k] = 0 for k < n (upper times lower): K starts at max(first row, first column)
   // Blocked triangular inverse, all pairs of neighbouring tri_b x tri_b diagonal blocks in one launch (tile sizes divide
   // tri_b): only the tiles of one off-diagonal block per pair are computed, over the K range of one block:
-  //   8: tile rows in an even block r, columns in block r+1, K = block r;   10: the same tiles, K = block r+1;
+  //   8: tile rows in an even block r, columns in block r+1, K = block r;
   //   9: tile rows in an odd block r, columns in block r-1, K = block r
-  // tri_d > 0 (modes 8-10): the matrices are an identity block beyond row and column tri_d; tiles of the odd block that
+  // tri_d > 0 (modes 8, 9): the matrices are an identity block beyond row and column tri_d; tiles of the odd block that
   // lie wholly beyond it return (their outputs are zero and stay unwritten) and K ranges over the odd block end at tri_d.
   int tri, tri_b, tri_d;
 };
@@ -412,6 +412,10 @@ __global__ __launch_bounds__(WGM * WGN * 64) __attribute__((amdgpu_waves_per_eu(
   // triangular products: tile rows differ in work by an order of magnitude, so neighbouring tiles go to different
   // XCDs (the hardware's own round-robin) instead of one contiguous range per XCD, the longest K ranges first
   if (p.tri != 0 && p.tri < 8) lb0 = p.tri == 1 ? (int)gridDim.x - 1 - (int)blockIdx.x : (int)blockIdx.x;
+  if (p.tri == 4 && (gridDim.x & 63) == 0) {    // runs of eight consecutive tiles per XCD (they share an operand panel in its L2), runs interleaved
+    const int i = (int)blockIdx.x >> 3, x = (int)blockIdx.x & 7;
+    lb0 = ((((i >> 3) << 3) + x) << 3) + (i & 7);
+  }
   int phase = 0;
   if (p.phases == 4) { phase = lb0 & 3; lb0 >>= 2; }   // the four phases of a tile run side by side: they read the same input
   const int split = INTERIOR ? 0 : lb0 / p.tiles_mn;
@@ -427,6 +431,16 @@ __global__ __launch_bounds__(WGM * WGN * 64) __attribute__((amdgpu_waves_per_eu(
     const int tiles_m = p.tiles_mn / p.tiles_n;
     tile_n = lb / tiles_m;
     tile_m = lb - tile_n * tiles_m;
+  }
+  if (p.tri == 4 && p.tiles_mn == p.tiles_n * p.tiles_n) {
+    // K range [max(row, column), K): on a square tile grid walk the L-shaped shells max(tile row, tile column) = 0, 1, ...
+    // so that the workgroups are dispatched longest first and the hardware's in-order dispatch balances the rest
+    int sh = (int)sqrtf((float)lb);
+    while (sh * sh > lb) --sh;
+    while ((sh + 1) * (sh + 1) <= lb) ++sh;
+    const int r = lb - sh * sh;                 // 0 .. 2 sh
+    tile_m = r <= sh ? r : sh;
+    tile_n = r <= sh ? sh : r - sh - 1;
   }
   if (p.tri >= 8) {                             // only the tiles of one off-diagonal block per pair are launched
     const int tbm = p.tri_b / BM, tbn = p.tri_b / BN, per_pair = tbm * tbn;
@@ -475,11 +489,11 @@ __global__ __launch_bounds__(WGM * WGN * 64) __attribute__((amdgpu_waves_per_eu(
   else if (p.tri >= 8) {
     const int rb = (int)(m0 / p.tri_b), cb = n0 / p.tri_b;
     if (p.tri == 9 ? !((rb & 1) == 1 && cb == rb - 1) : !((rb & 1) == 0 && cb == rb + 1)) return;
-    k_lo = (p.tri == 10 ? rb + 1 : rb) * p.tri_b;
+    k_lo = rb * p.tri_b;
     k_hi = k_lo + p.tri_b;
     if (p.tri_d > 0) {
       if ((p.tri == 9 ? m0 : (int64_t)n0) >= p.tri_d) return;
-      if (p.tri != 8) k_hi = min(k_hi, p.tri_d);
+      if (p.tri == 9) k_hi = min(k_hi, p.tri_d);
     }
   }
   const int kt_lo = k_lo / BK, kt_hi = (k_hi + BK - 1) / BK;
@@ -1007,10 +1021,10 @@ int launch_conv_mfma(const ConvArgs& a0, hipStream_t s) {
   p.tri = a0.tri;
   p.tri_b = a0.tri_b;
   p.tri_d = a0.tri >= 8 ? a0.tri_d : 0;
-  if (a0.tri >= 8 && (a0.tri > 10 || a.dtype != AE_F32 || a0.tri_b < 128 || a0.tri_b % 128 != 0 || a.n % (2 * a0.tri_b) != 0 ||
+  if (a0.tri >= 8 && (a0.tri > 9 || a.dtype != AE_F32 || a0.tri_b < 128 || a0.tri_b % 128 != 0 || a.n % (2 * a0.tri_b) != 0 ||
                       a0.tri_d < 0 || a0.tri_d > a.n || a0.tri_d % 128 != 0))
     return fail(AE_EINVAL, "conv_mfma: bad block size for the blocked triangular inverse");
-  if (a0.tri != 0 && (a0.tri < 0 || (a0.tri > 4 && a0.tri < 8) || a0.tri > 10 || a.k != 1 || a.hc != 1 || a.wc != 1 || a.up != 0 || a.n != a.cout || a.cin != a.cout ||
+  if (a0.tri != 0 && (a0.tri < 0 || (a0.tri > 4 && a0.tri < 8) || a0.tri > 9 || a.k != 1 || a.hc != 1 || a.wc != 1 || a.up != 0 || a.n != a.cout || a.cin != a.cout ||
                       a0.epi != CONV_EPI_NONE || a.partial))
     return fail(AE_EINVAL, "conv_mfma: triangular K ranges are for square dense products only");
   p.x_bytes = (unsigned)((int64_t)a.n * (a.hc >> a.up) * (a.wc >> a.up) * a.cin * es);

@@ -158,7 +158,6 @@ struct ConvArgs {
   //                         blocks (r even, r+1) in one launch; only the tiles of the named off-diagonal block of
   //                         each pair are computed, over the K range of the named block:
   //                           UPPER_K0: rows in block r, columns in block r+1, K = block r;
-  //                           UPPER_K1: the same tiles, K = block r+1;
   //                           LOWER_K1: rows in block r+1, columns in block r, K = block r+1.
   //                         tri_pairs > 0 limits the launch to the first tri_pairs pairs (the rest keep their contents).
   int tri = 0;
@@ -169,7 +168,7 @@ struct ConvArgs {
   int tri_d = 0;
 };
 enum { CONV_TRI_NONE = 0, CONV_TRI_LOWER_UPPER = 1, CONV_TRI_UPPER_X = 2, CONV_TRI_UPPER_W = 3, CONV_TRI_UPPER_LOWER = 4,
-       CONV_TRI_PAIR_UPPER_K0 = 8, CONV_TRI_PAIR_LOWER_K1 = 9, CONV_TRI_PAIR_UPPER_K1 = 10 };
+       CONV_TRI_PAIR_UPPER_K0 = 8, CONV_TRI_PAIR_LOWER_K1 = 9 };
 enum { CONV_PLAIN = 0, CONV_UP_PHASES = 1, CONV_UP_DGRAD = 2 };
 enum { CONV_EPI_NONE = 0, CONV_EPI_MXQ = 1, CONV_EPI_RESID = 2 };
 bool conv_epi_usable(const ConvArgs& a);         // can launch_conv_mfma run a.epi for this shape?
