@@ -254,10 +254,67 @@ __global__ __launch_bounds__(256) void k_tri_prepare(LuSrc q, int dp, float* __r
   }
 }
 
+// One merge level of the in-LDS recursion: for every pair p of neighbouring B x B diagonal blocks of the 128 x 128
+// matrix, X21 = -X22 (M21 X11) into xb below the diagonal blocks.  64 / B pairs, 256 threads, each a TR x TC register
+// tile of outputs (rows tr + (B/TR) i, columns tc + (B/TC) j: neighbouring threads read neighbouring LDS columns).
+// X11 and X22 are lower triangular inside xb, whose other entries are zero, so the K ranges are cut per thread only:
+// the first product starts at the thread's first column, the second ends at its last row.  Ends on a barrier.
+template <int B, int TR, int TC>
+__device__ __forceinline__ void tri128_merge(float (*mb)[129], float (*xb)[129], float* tb, int tid) {
+  constexpr int PAIRS = 64 / B, TPP = 256 / PAIRS, TCN = B / TC, TRN = B / TR;
+  static_assert(TRN * TCN == TPP, "one register tile per thread");
+  const int p = tid / TPP, t = tid % TPP, tr = t / TCN, tc = t % TCN;
+  const int o0 = 2 * p * B, o1 = o0 + B;             // first row / column of the pair's two diagonal blocks
+  float* tp = tb + p * B * B;
+  float acc[TR][TC];
+#pragma unroll
+  for (int i = 0; i < TR; ++i)
+#pragma unroll
+    for (int j = 0; j < TC; ++j) acc[i][j] = 0.0f;
+#pragma unroll 4
+  for (int k = tc; k < B; ++k) {                       // T = M21 X11:  X11[k][c] = 0 for k < c, and c >= tc
+    float a[TR], x[TC];
+#pragma unroll
+    for (int i = 0; i < TR; ++i) a[i] = mb[o1 + tr + TRN * i][o0 + k];
+#pragma unroll
+    for (int j = 0; j < TC; ++j) x[j] = xb[o0 + k][o0 + tc + TCN * j];
+#pragma unroll
+    for (int i = 0; i < TR; ++i)
+#pragma unroll
+      for (int j = 0; j < TC; ++j) acc[i][j] = fmaf(a[i], x[j], acc[i][j]);
+  }
+#pragma unroll
+  for (int i = 0; i < TR; ++i)
+#pragma unroll
+    for (int j = 0; j < TC; ++j) {
+      tp[(tr + TRN * i) * B + tc + TCN * j] = acc[i][j];
+      acc[i][j] = 0.0f;
+    }
+  __syncthreads();
+  const int kend = tr + TRN * (TR - 1);                // X21 = -X22 T:  X22[r][k] = 0 for k > r, and r <= kend
+#pragma unroll 4
+  for (int k = 0; k <= kend; ++k) {
+    float a[TR], x[TC];
+#pragma unroll
+    for (int i = 0; i < TR; ++i) a[i] = xb[o1 + tr + TRN * i][o1 + k];
+#pragma unroll
+    for (int j = 0; j < TC; ++j) x[j] = tp[k * B + tc + TCN * j];
+#pragma unroll
+    for (int i = 0; i < TR; ++i)
+#pragma unroll
+      for (int j = 0; j < TC; ++j) acc[i][j] = fmaf(a[i], x[j], acc[i][j]);
+  }
+#pragma unroll
+  for (int i = 0; i < TR; ++i)
+#pragma unroll
+    for (int j = 0; j < TC; ++j) xb[o1 + tr + TRN * i][o0 + tc + TCN * j] = -acc[i][j];   // (below the diagonal blocks: nobody reads it in this pass)
+  __syncthreads();
+}
+
 // xb = mb^-1 for a lower triangular 128 x 128 matrix in LDS (all 256 threads of the workgroup; xb must be zero on
 // entry and both arrays visible to every thread; ends on a barrier): 16 x 16 diagonal blocks by forward substitution
-// (thread j solves column j of its block), then three levels of merges [[X11, 0], [-X22 M21 X11, X22]] with all
-// threads sharing the outputs of the two small products.  tb: 64 * 64 values of scratch.
+// (thread j solves column j of its block), then three levels of merges [[X11, 0], [-X22 M21 X11, X22]] (tri128_merge).
+// tb: 64 * 64 values of scratch.
 __device__ __forceinline__ void tri128_inverse_lds(float (*mb)[129], float (*xb)[129], float* tb, int tid) {
   if (tid < 128) {                                     // column tid of its 16 x 16 diagonal block
     const int j = tid, b0 = j & ~15;
@@ -268,38 +325,9 @@ __device__ __forceinline__ void tri128_inverse_lds(float (*mb)[129], float (*xb)
     }
   }
   __syncthreads();
-  for (int b = 16; b < 128; b *= 2) {
-    const int lb = b == 16 ? 4 : (b == 32 ? 5 : 6);    // log2 b
-    // T[p][r][c] = sum_k M21[r][k] X11[k][c], X11 lower triangular: k >= c   (pairs * b * b = 64 b values)
-    for (int e = tid; e < 64 * b; e += 256) {
-      const int p = e >> (2 * lb), r = (e >> lb) & (b - 1), c = e & (b - 1);
-      const int r1 = (2 * p + 1) * b + r, c0 = 2 * p * b;
-      float a0 = 0.0f, a1 = 0.0f;
-      int k = c;
-      for (; k + 2 <= b; k += 2) {
-        a0 = fmaf(mb[r1][c0 + k], xb[c0 + k][c0 + c], a0);
-        a1 = fmaf(mb[r1][c0 + k + 1], xb[c0 + k + 1][c0 + c], a1);
-      }
-      if (k < b) a0 = fmaf(mb[r1][c0 + k], xb[c0 + k][c0 + c], a0);
-      tb[e] = a0 + a1;
-    }
-    __syncthreads();
-    // X21[r][c] = -sum_k X22[r][k] T[k][c], X22 lower triangular: k <= r
-    for (int e = tid; e < 64 * b; e += 256) {
-      const int p = e >> (2 * lb), r = (e >> lb) & (b - 1), c = e & (b - 1);
-      const int r1 = (2 * p + 1) * b, c0 = 2 * p * b;
-      const float* t = tb + (p << (2 * lb));
-      float a0 = 0.0f, a1 = 0.0f;
-      int k = 0;
-      for (; k + 2 <= r + 1; k += 2) {
-        a0 = fmaf(xb[r1 + r][r1 + k], t[(k << lb) + c], a0);
-        a1 = fmaf(xb[r1 + r][r1 + k + 1], t[((k + 1) << lb) + c], a1);
-      }
-      if (k <= r) a0 = fmaf(xb[r1 + r][r1 + k], t[(k << lb) + c], a0);
-      xb[r1 + r][c0 + c] = -(a0 + a1);               // (below the diagonal blocks: nobody reads it in this pass)
-    }
-    __syncthreads();
-  }
+  tri128_merge<16, 2, 2>(mb, xb, tb, tid);
+  tri128_merge<32, 2, 4>(mb, xb, tb, tid);
+  tri128_merge<64, 4, 4>(mb, xb, tb, tid);
 }
 
 // X_bb = M_bb^-1 for every 128 x 128 diagonal block b (one workgroup of 256 threads each) by the recursion above;
