@@ -277,6 +277,45 @@ def test_backward_two_streams_same_bits(ae, dtype, spec, batch):
         assert np.array_equal(got[0], got[k]), "call %d differs from the single-stream result" % k
 
 
+def test_forward_and_backward_replay_from_a_captured_graph(ae):
+    """The calls make no allocation and no host synchronisation, and the library's second stream is forked from and
+    joined into the caller's by events, so a caller may capture them into a HIP graph: four replays, with eager calls
+    (same handle, other buffers) and synchronisations between them, each bit for bit the eager result."""
+    import torch
+    cfg = wl.CONFIGS["cfg2"]
+    spec, batch = cfg["spec"], 32
+    m = ae.Model(spec, batch, ae.DTYPES["f32"])
+    params = torch.from_numpy(wl.make_params(spec, 11)).cuda()
+    x = torch.from_numpy(wl.make_input(spec, batch, 11)).cuda().contiguous()
+    y0 = torch.empty((batch,) + m.out_shape, device="cuda")
+    y1 = torch.full_like(y0, float("nan"))
+    dy = torch.from_numpy(wl.make_cotangent((batch,) + m.out_shape, 11)).cuda().contiguous()
+    g0 = torch.empty(m.n_params, device="cuda")
+    g1 = torch.full_like(g0, float("nan"))
+
+    def run(y, g):
+        m.model_forward(params, x, 10.0, 11, y)
+        m.model_backward(params, x, dy, g)
+
+    run(y0, g0)
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(graph, stream=s):
+        run(y1, g1)
+    for _ in range(4):
+        y1.fill_(float("nan"))
+        g1.fill_(float("nan"))
+        run(y0, g0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y0, y1) and torch.equal(g0, g1)
+    del graph
+    m.close()
+
+
 # ------------------------------------------------------------------ error handling (host side, no kernel faults)
 def test_error_codes(ae):
     import torch
