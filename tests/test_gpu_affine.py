@@ -466,3 +466,33 @@ def test_small_batch_argument_checks(ae):
     assert ae.lib.model_lu_compose_batch(None, p, p, p, p, 1, 64, 0, p, None) == -1
     assert ae.lib.model_lu_backward_batch(p, p, p, p, p, p, 1, 0, 0, p, p, p, None) == -1
     assert ae.lib.model_lu_inverse_batch(p, p, p, p, None, 1, 64, 0, p, None) == -1
+
+
+def test_index_vector_that_is_not_a_permutation_stays_inside_the_arrays(ae):
+    """perm is not trusted: an entry outside 0..d-1 is treated as its own position (every kernel that indexes with it
+    checks the range), so A is still defined row by row; the gradient and inverse calls must complete with finite
+    results (which rows they produce is unspecified for such input)."""
+    import torch
+    d = 128
+    lp, up, ls, sg, perm = wl.make_lu_params(d, seed=41)
+    bad = perm.copy()
+    bad[[3, 50, 127]] = [-1, d, 1 << 30]
+    fixed = bad.copy()
+    fixed[[3, 50, 127]] = [3, 50, 127]
+    ref = ao.lu_compose(lp, up, ls, sg, fixed)
+    assert _close(_compose(ae, (lp, up, ls, sg, bad), d, "f32"), ref, TOL["f32"])
+    dev = [torch.from_numpy(np.ascontiguousarray(a[None])).cuda() for a in (lp, up, ls, sg, bad)]
+    a = torch.full((1, d, d), float("nan"), device="cuda")
+    ae.model_lu_compose_batch(*dev, 1, d, a)
+    assert _close(a[0].cpu().numpy().astype(np.float64), ref, TOL["f32"])
+    g = np.random.default_rng(3).standard_normal((d, d))
+    for out in _backward(ae, g, (lp, up, ls, sg, bad), d, "f32") + [_inverse(ae, (lp, up, ls, sg, bad), d, "f32")]:
+        assert np.all(np.isfinite(out))
+    gt = torch.from_numpy(g.astype(np.float32)[None]).cuda()
+    dlp, dup, dls = torch.empty((1, d, d), device="cuda"), torch.empty((1, d, d), device="cuda"), torch.empty((1, d), device="cuda")
+    ainv = torch.empty((1, d, d), device="cuda")
+    ae.model_lu_backward_batch(gt, *dev, 1, d, dlp, dup, dls)
+    ae.model_lu_inverse_batch(*dev, 1, d, ainv)
+    torch.cuda.synchronize()
+    for t in (dlp, dup, dls, ainv):
+        assert bool(torch.isfinite(t).all())
