@@ -131,8 +131,12 @@ template <> struct MxFormat<MX_FP8> {
   static __device__ __forceinline__ float quant(float v, float inv_s, float s) {
     const float y = v * inv_s;                   // exact, |y| < 512
     const float a = fabsf(y);
-    const int e = a < 0.015625f ? -6 : ilogbf(a);                 // binade of the value; subnormals share the spacing of 2^-6
-    const float r = rintf(a * ldexpf(1.0f, 3 - e)) * ldexpf(1.0f, e - 3);   // three mantissa bits: exact in binary32
+    // normal range: round the binary32 mantissa to its three leading bits, to nearest, ties to even (a carry runs
+    // into the exponent, as it should); below 2^-6 the format's subnormals have the fixed spacing 2^-9
+    const uint32_t b = __float_as_uint(a);
+    const float rn = __uint_as_float((b + 0x7FFFFu + ((b >> 20) & 1u)) & 0xFFF00000u);
+    const float rs = rintf(a * 512.0f) * 0.001953125f;
+    const float r = a < 0.015625f ? rs : rn;
     return copysignf(fminf(r, 448.0f), y) * s;
   }
 };
