@@ -511,6 +511,19 @@ def bench_qr_param(torch, ae, args):
     per_step = launches // steps
     flops_per_launch = 2.0 * d ** 3
     ach = flops_per_launch / avg_ms / 1e9
+    # beside the step: A^-1 = (R + diag s)^-1 Q^T from the workspace the last compose left
+    ae.model_qr_compose(g, rp, ls, sg, d, a, ws, squarings)
+    ainv = torch.empty((d, d), dtype=td, device="cuda")
+    wsi = torch.empty(ae.model_lu_inverse_workspace(d), dtype=torch.uint8, device="cuda")
+    for _ in range(2):
+        ae.model_qr_inverse(rp, ls, sg, d, ws, ainv, wsi, squarings)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        ae.model_qr_inverse(rp, ls, sg, d, ws, ainv, wsi, squarings)
+    e1.record()
+    torch.cuda.synchronize()
+    inv_ms = e0.elapsed_time(e1) / 5
     from oracle import affine_oracle as ao
     cpu = None
     if not args.no_cpu_baseline:
@@ -532,7 +545,8 @@ def bench_qr_param(torch, ae, args):
         "ms_per_step": dt / steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "qr_param: A = exp((G - G^T)/2)(R + diag s), d = 4096, block-orthogonal initialisation + noise",
-                   "d": d, "squarings": squarings, "taylor_order": 8, "storage_of_A_and_dA": args.dtype},
+                   "d": d, "squarings": squarings, "taylor_order": 8, "storage_of_A_and_dA": args.dtype,
+                   "inverse_ms_beside_the_step": inv_ms},
         "roofline": {"bound": "mfma", "kernel": "k_igemm<float> (dense)", "achieved": ach, "peak": PEAK["f32"], "unit": "TFLOP/s",
                      "frac": ach / PEAK["f32"], "traffic": QR_TRAFFIC_BYTES.get("f32"), "avg_ms": avg_ms,
                      "launches_per_step": per_step, "flops_per_launch": flops_per_launch, "bytes_per_launch": 3.0 * d * d * 4},
