@@ -886,10 +886,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
 struct IgemmTile { int bm, bn, bkb; };
 
 // Largest tile that still gives every compute unit about two workgroups.
-IgemmTile pick_tile(int64_t M, int cout, int cin, int es, bool wide = true) {
+IgemmTile pick_tile(int64_t M, int cout, int cin, int es, bool wide = true, int min_wide_tiles = 256) {
   // large dense bf16 products whose 256 x 256 tiles all lie inside the output and still fill the chip: eight
   // wavefronts per workgroup, a third fewer operand bytes through LDS per multiply-add than 256 x 128
-  if (wide && es == 2 && cout % 256 == 0 && M % 256 == 0 && (M / 256) * (cout / 256) >= 256) return IgemmTile{256, 256, 64};
+  if (wide && es == 2 && cout % 256 == 0 && M % 256 == 0 && (M / 256) * (cout / 256) >= min_wide_tiles) return IgemmTile{256, 256, 64};
   const int bn = cout > 64 ? 128 : 64;
   const int64_t tiles_n = (cout + bn - 1) / bn;
   int bm = es == 2 ? 256 : 128;                 // 256-row tiles: bf16 only (register budget)
@@ -1057,9 +1057,10 @@ int launch_conv_mfma(const ConvArgs& a0, hipStream_t s) {
 #undef PATCH_LAUNCH_W
     return launch_status("conv3_patch");
   }
-  // the wide tile exists without run-time checks only; tiles of very different K lengths balance better when smaller
-  const bool wide_ok = a0.tri == 0 && !a.y_aux && a.act != ACT_SIGMOID && !(a.partial && a.act != ACT_NONE) && a0.geom == CONV_PLAIN;
-  const IgemmTile t = pick_tile(p.M, a.cout, a.cin, es, wide_ok);
+  // the wide tile exists without run-time checks only; tiles of very different K lengths (the triangular modes 1-3)
+  // balance better when smaller unless there are at least four per compute unit (measured: d = 8192, not 4096)
+  const bool wide_ok = (a0.tri == 0 || a0.tri <= 3) && !a.y_aux && a.act != ACT_SIGMOID && !(a.partial && a.act != ACT_NONE) && a0.geom == CONV_PLAIN;
+  const IgemmTile t = pick_tile(p.M, a.cout, a.cin, es, wide_ok, a0.tri == 0 ? 256 : 1024);
   p.tiles_n = (a.cout + t.bn - 1) / t.bn;
   const int64_t tiles_m = (p.M + t.bm - 1) / t.bm;
   const int KT = (int)((int64_t)p.K * es / t.bkb);

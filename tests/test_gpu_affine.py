@@ -241,6 +241,12 @@ def test_largest_size_exercised(ae):
     resid = a_ref @ inv[:, cols]
     resid[cols, np.arange(len(cols))] -= 1.0
     assert np.abs(resid).max() < 1e-4
+    del inv, resid, a_ref
+    # the gradients at this size (the triangular products switch to 256 x 256 tiles here)
+    g = wl.round_to_bf16(np.random.default_rng(18).standard_normal((d, d)).astype(np.float32)).astype(np.float64)
+    dlp, dup, dls = _backward(ae, g, params, d, "bf16")
+    r_lp, r_up, r_ls = ao.lu_gradients(g, *params)
+    assert _close(dlp, r_lp, TOL["bf16"]) and _close(dup, r_up, TOL["bf16"]) and _close(dls, r_ls, TOL["bf16"])
 
 
 def test_inverse_feeds_the_transformation_error(ae):
