@@ -206,10 +206,11 @@ def bench_transform_mse(torch, ae, args):
     bf = args.dtype == "bf16"
     td = torch.bfloat16 if bf else torch.float32
     x_h = wl.make_activations(rows, d, seed=9, bf16=bf)
-    a, v, ainv, ishift = wl.make_transform(d, seed=9, bf16=bf, kind="affine")
+    a, v, ainv = wl.make_transform(d, seed=9, bf16=bf, kind="affine")
     dev = lambda arr, t: torch.from_numpy(np.ascontiguousarray(arr, dtype=np.float32)).cuda().to(t).contiguous()
     x, at, ait = dev(x_h, td), dev(a, td), dev(ainv, td)
-    vt, st = dev(v, torch.float32), dev(ishift, torch.float32)
+    vt, st = dev(v, torch.float32), torch.empty(d, device="cuda")
+    ae.model_inverse_shift(ait, vt, d, st)
     yq = torch.empty_like(x)
     ws = torch.empty(ae.model_transform_mse_workspace(rows, d, ae.DTYPES[args.dtype]) // 4, dtype=torch.float32, device="cuda")
     eb = torch.empty(d // block, device="cuda")
@@ -397,8 +398,8 @@ def bench_fold(torch, ae, args):
     bf = args.dtype == "bf16"
     td = torch.bfloat16 if bf else torch.float32
     rng = np.random.default_rng(21)
-    a1, v1, a1inv, _ = wl.make_transform(d, seed=21, bf16=bf, kind="affine")
-    a2, v2, a2inv, _ = wl.make_transform(dh, seed=22, bf16=bf, kind="affine")
+    a1, v1, a1inv = wl.make_transform(d, seed=21, bf16=bf, kind="affine")
+    a2, v2, a2inv = wl.make_transform(dh, seed=22, bf16=bf, kind="affine")
     dev = lambda a, t=td: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda().to(t).contiguous()
     f32 = torch.float32
     layers = []            # (name, out, in, a_left, v_left, a_right_inv, v_right)

@@ -155,6 +155,11 @@ int model_count_errors(const float* y, const float* x_pm1, int64_t batch, int k,
 int model_num_steps(const ae_model* m, int* n_steps);
 int model_step_info(const ae_model* m, int step, int* last_token, int64_t chw[3]);
 int model_get_activation(ae_model* m, int step, float* out_nchw, void* stream);
+/* A step that applies batch-norm and/or max-pooling keeps the convolution's own output (bias included, before
+ * batch-norm, activation and pooling) for the backward pass, which takes its ReLU masks and pool winners from it.
+ * chw (nullable) receives that tensor's shape, out_nchw (nullable: query the shape only) the tensor as binary32
+ * NCHW.  AE_EINVAL for a step that keeps no such tensor, AE_ESTATE before the first forward pass. */
+int model_get_conv_output(ae_model* m, int step, int64_t chw[3], float* out_nchw, void* stream);
 
 /* Per-kernel timing for benchmarks.  While enabled, every kernel the executor
  * launches is bracketed by two HIP events on the caller's stream (a few
@@ -207,6 +212,10 @@ int model_mx_quantize_elem(const void* x, void* q, int64_t rows, int64_t d, int 
  * workspace: model_transform_mse_workspace bytes of device memory.  block: a power of two, 8 (bf16) / 4 (fp32) to 64; d a multiple of
  * 128, rows a multiple of 256 (bf16) or 128 (fp32), every tensor below 2 GiB: AE_EINVAL otherwise. */
 int model_transform_mse_workspace(int64_t rows, int64_t d, int dtype, int64_t* bytes);
+/* The constant term of the inverse map of the same definition, T^-1(y) = A^-1 y - A^-1 v:
+ * inv_shift[i] = -sum_j a_inv[i][j] v[j]  (a_inv [d][d] row-major in dtype, v and inv_shift binary32 [d], device;
+ * double-precision accumulation).  1 <= d <= 46340, AE_EINVAL otherwise. */
+int model_inverse_shift(const void* a_inv, const float* v, int64_t d, int dtype, float* inv_shift, void* stream);
 int model_transform_mse(const void* x, const void* a_mat, const float* v, const void* a_inv, const float* inv_shift,
                         int64_t rows, int64_t d, int block, int dtype, void* yq, void* workspace, float* e_blocks,
                         float* e_total, void* stream);

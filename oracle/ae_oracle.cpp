@@ -757,7 +757,7 @@ int oracle_forward(void* h, const float* params, const float* x, float snr_db, u
 // Copy the output of op i (i = -1: input) saved by the last forward.
 int64_t oracle_get_activation(void* h, int i, double* out) {
   Net* net = (Net*)h;
-  if (!net->have_forward) return -1;
+  if (!net->have_forward || i < -1 || i + 1 >= (int)net->acts.size()) return -1;
   const std::vector<double>& a = net->acts[i + 1];
   if (out) std::memcpy(out, a.data(), a.size() * sizeof(double));
   return (int64_t)a.size();

@@ -22,8 +22,8 @@ SYMBOLS = [
     "model_describe", "model_create", "model_destroy", "model_param_count", "model_io_shape",
     "model_set_sample_offset", "model_forward", "model_backward", "model_loss_mse", "model_noise",
     "model_pnorm_awgn", "model_gen_bits", "model_count_errors", "model_num_steps", "model_step_info",
-    "model_get_activation", "model_timing_enable", "model_set_overlap", "model_calibrate_mfma", "model_mx_quantize", "model_mx_quantize_elem", "model_transform_mse_workspace",
-    "model_transform_mse", "model_transform_mse_elem", "model_lu_workspace", "model_lu_compose", "model_lu_backward", "model_vol_penalty", "model_lu_inverse_workspace", "model_lu_inverse", "model_lu_compose_batch", "model_lu_backward_batch", "model_lu_inverse_batch", "model_lu_timing", "model_qr_workspace", "model_qr_compose", "model_qr_backward", "model_qr_inverse", "model_fold_workspace", "model_fold_linear", "model_fold_embedding", "model_timing_slots",
+    "model_get_activation", "model_get_conv_output", "model_timing_enable", "model_set_overlap", "model_calibrate_mfma", "model_mx_quantize", "model_mx_quantize_elem", "model_transform_mse_workspace",
+    "model_transform_mse", "model_transform_mse_elem", "model_inverse_shift", "model_lu_workspace", "model_lu_compose", "model_lu_backward", "model_vol_penalty", "model_lu_inverse_workspace", "model_lu_inverse", "model_lu_compose_batch", "model_lu_backward_batch", "model_lu_inverse_batch", "model_lu_timing", "model_qr_workspace", "model_qr_compose", "model_qr_backward", "model_qr_inverse", "model_fold_workspace", "model_fold_linear", "model_fold_embedding", "model_timing_slots",
     "model_timing_read", "model_timing_reset", "model_last_error",
 ]
 
@@ -57,6 +57,7 @@ def _load():
     L.model_num_steps.argtypes = [vp, C.POINTER(C.c_int)]
     L.model_step_info.argtypes = [vp, C.c_int, C.POINTER(C.c_int), i64p]
     L.model_get_activation.argtypes = [vp, C.c_int, vp, vp]
+    L.model_get_conv_output.argtypes = [vp, C.c_int, i64p, vp, vp]
     L.model_timing_enable.argtypes = [vp, C.c_int]
     L.model_set_overlap.argtypes = [vp, C.c_int]
     L.model_calibrate_mfma.argtypes = [C.c_int, C.c_int, C.c_int, vp, C.POINTER(C.c_double), C.POINTER(C.c_double), vp]
@@ -65,6 +66,7 @@ def _load():
     L.model_transform_mse_workspace.argtypes = [C.c_int64, C.c_int64, C.c_int, i64p]
     L.model_transform_mse.argtypes = [vp, vp, vp, vp, vp, C.c_int64, C.c_int64, C.c_int, C.c_int, vp, vp, vp, vp, vp]
     L.model_transform_mse_elem.argtypes = [vp, vp, vp, vp, vp, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp, vp]
+    L.model_inverse_shift.argtypes = [vp, vp, C.c_int64, C.c_int, vp, vp]
     L.model_lu_workspace.argtypes = [C.c_int64, C.c_int, i64p]
     L.model_lu_compose.argtypes = [vp, vp, vp, vp, vp, C.c_int64, C.c_int, vp, vp, vp]
     L.model_lu_backward.argtypes = [vp, vp, vp, vp, vp, vp, C.c_int64, C.c_int, vp, vp, vp, vp, vp]
@@ -208,6 +210,17 @@ class Model:
         _check(lib.model_get_activation(self._h, step, _ptr(out_nchw, torch.float32), _stream()))
 
 
+    def model_get_conv_output(self, step, out_nchw=None):
+        """Shape (C, H, W) of the convolution output step `step` keeps, or None if it keeps none; fills out_nchw if given."""
+        chw = (C.c_int64 * 3)()
+        rc = lib.model_get_conv_output(self._h, step, chw, _ptr(out_nchw, torch.float32) if out_nchw is not None else C.c_void_p(0),
+                                       _stream())
+        if rc == -1 and out_nchw is None:
+            return None
+        _check(rc)
+        return tuple(chw)
+
+
 def _prod(s):
     p = 1
     for v in s:
@@ -268,6 +281,12 @@ def model_transform_mse(x, a_mat, v, a_inv, inv_shift, rows, d, block, yq, works
     _check(lib.model_transform_mse(_ptr(x), _ptr(a_mat), _ptr(v, torch.float32), _ptr(a_inv), _ptr(inv_shift, torch.float32),
                                    rows, d, block, dtype, _ptr(yq), _ptr(workspace), _ptr(e_blocks, torch.float32),
                                    _ptr(e_total, torch.float32), _stream()))
+
+
+def model_inverse_shift(a_inv, v, d, inv_shift):
+    dtype = AE_BF16 if a_inv.dtype == torch.bfloat16 else AE_F32
+    assert a_inv.numel() == d * d and v.numel() == d and inv_shift.numel() == d
+    _check(lib.model_inverse_shift(_ptr(a_inv), _ptr(v, torch.float32), d, dtype, _ptr(inv_shift, torch.float32), _stream()))
 
 
 def model_lu_workspace(d, dtype):

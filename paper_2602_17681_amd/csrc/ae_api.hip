@@ -813,4 +813,16 @@ int model_get_activation(ae_model* m, int step, float* out_nchw, void* stream) {
   return launch_to_f32_nchw(st.out, out_nchw, P.batch, st.cout, st.hout * st.wout, P.dtype, (hipStream_t)stream);
 }
 
+int model_get_conv_output(ae_model* m, int step, int64_t chw[3], float* out_nchw, void* stream) {
+  if (!m || step < 0 || step >= (int)m->plan.steps.size()) return fail(AE_EINVAL, "model_get_conv_output: bad argument");
+  const Plan& P = m->plan;
+  const Step& st = P.steps[step];
+  if (st.kind != ST_CONV || !(st.has_bn || st.pool) || !st.raw)
+    return fail(AE_EINVAL, "model_get_conv_output: step %d keeps no convolution output apart from its saved output", step);
+  if (chw) { chw[0] = st.cout; chw[1] = st.hc; chw[2] = st.wc; }
+  if (!out_nchw) return AE_OK;
+  if (!m->have_forward) return fail(AE_ESTATE, "model_get_conv_output: no forward pass yet");
+  return launch_to_f32_nchw(st.raw, out_nchw, P.batch, st.cout, st.hc * st.wc, P.dtype, (hipStream_t)stream);
+}
+
 }  // extern "C"

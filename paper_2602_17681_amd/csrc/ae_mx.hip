@@ -115,6 +115,20 @@ __global__ void k_mse_total(const float* __restrict__ eb, int nb, float* __restr
   if (threadIdx.x == 0) *e = (float)(acc / (double)nb);
 }
 
+// The constant term of the inverse map of Definition 3.1, T^-1(y) = A^-1 y - A^-1 v:  out[i] = -sum_j ainv[i][j] v[j].
+// One wavefront per row; products and sums in double (d of them per row: nothing to gain from less).
+template <typename T>
+__global__ __launch_bounds__(NT) void k_inverse_shift(const T* __restrict__ ainv, const float* __restrict__ v, int d,
+                                                      float* __restrict__ out) {
+  const int row = blockIdx.x * (NT / 64) + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (row >= d) return;
+  const T* r = ainv + (int64_t)row * d;
+  double acc = 0.0;
+  for (int j = lane; j < d; j += 64) acc += (double)Store<T>::ld(r + j) * (double)v[j];
+  acc = wave_sum(acc);
+  if (lane == 0) out[row] = (float)(-acc);
+}
+
 int transform_tile_rows(int64_t rows, int64_t d, int dtype) {
   ConvArgs a;
   memset(&a, 0, sizeof(a));
@@ -181,6 +195,19 @@ extern "C" int model_transform_mse_elem(const void* x, const void* a_mat, const 
                      1.0 / ((double)rows * (double)block), e_blocks);
   hipLaunchKernelGGL(k_mse_total, dim3(1), dim3(NT), 0, s, e_blocks, nb, e_total);
   return launch_status("transform_mse");
+}
+
+extern "C" int model_inverse_shift(const void* a_inv, const float* v, int64_t d, int dtype, float* inv_shift, void* stream) {
+  using namespace ae;
+  if (!a_inv || !v || !inv_shift) return fail(AE_EINVAL, "model_inverse_shift: null argument");
+  if (dtype != AE_F32 && dtype != AE_BF16) return fail(AE_EINVAL, "model_inverse_shift: bad dtype");
+  if (d <= 0 || d > 46340) return fail(AE_EINVAL, "model_inverse_shift: d must be 1 .. 46340");
+  const unsigned blocks = (unsigned)((d + NT / 64 - 1) / (NT / 64));
+  if (dtype == AE_BF16)
+    hipLaunchKernelGGL(k_inverse_shift<bf16_t>, dim3(blocks), dim3(NT), 0, (hipStream_t)stream, (const bf16_t*)a_inv, v, (int)d, inv_shift);
+  else
+    hipLaunchKernelGGL(k_inverse_shift<float>, dim3(blocks), dim3(NT), 0, (hipStream_t)stream, (const float*)a_inv, v, (int)d, inv_shift);
+  return launch_status("inverse_shift");
 }
 
 extern "C" int model_mx_quantize_elem(const void* x, void* q, int64_t rows, int64_t d, int block, int elem, int dtype, void* stream) {

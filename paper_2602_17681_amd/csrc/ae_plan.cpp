@@ -33,18 +33,37 @@ struct Tok {
   int a = 0, b = 0, c = 0;  // conv: k, cout; fc: cout; reshape: c,h,w
 };
 
-bool read_dims(const std::string& s, int* c, int* h, int* w) {
-  int n = 0;
-  if (sscanf(s.c_str(), "%dx%dx%d%n", c, h, w, &n) != 3 || n != (int)s.size()) return false;
-  return *c > 0 && *h > 0 && *w > 0;
-}
-
+// a positive decimal integer of at most 9 digits (so it fits an int with room to spare), nothing else
 bool read_int(const std::string& s, int* v) {
   if (s.empty() || s.size() > 9) return false;
-  for (char ch : s)
+  int64_t acc = 0;
+  for (char ch : s) {
     if (ch < '0' || ch > '9') return false;
-  *v = atoi(s.c_str());
-  return *v > 0;
+    acc = acc * 10 + (ch - '0');
+  }
+  *v = (int)acc;
+  return acc > 0;
+}
+
+// "CxHxW": three such integers
+bool read_dims(const std::string& s, int* c, int* h, int* w) {
+  const size_t p1 = s.find('x');
+  if (p1 == std::string::npos) return false;
+  const size_t p2 = s.find('x', p1 + 1);
+  if (p2 == std::string::npos) return false;
+  return read_int(s.substr(0, p1), c) && read_int(s.substr(p1 + 1, p2 - p1 - 1), h) && read_int(s.substr(p2 + 1), w);
+}
+
+// Every tensor of a model (activations of the whole batch, weights of a layer) must stay below 2 GiB in
+// binary32: the kernels index elements with 32-bit integers and address memory through 32-bit buffer ranges.
+constexpr int64_t kMaxTensorElems = ((int64_t)1 << 29) - 1;
+bool tensor_fits(int64_t batch, int64_t c, int64_t h, int64_t w) {
+  if (c > kMaxTensorElems || h > kMaxTensorElems || w > kMaxTensorElems) return false;
+  const int64_t hw = h * w;                       // < 2^58
+  if (hw > kMaxTensorElems) return false;
+  const int64_t chw = c * hw;                     // < 2^58
+  if (chw > kMaxTensorElems) return false;
+  return batch * chw <= kMaxTensorElems;          // batch < 2^31: < 2^60
 }
 
 int tokenize(const char* spec, int* c0, int* h0, int* w0, std::vector<Tok>* toks) {
@@ -103,7 +122,9 @@ int build_plan(const char* spec, int batch, int dtype, int bn_mode, Plan* plan) 
   std::vector<Tok> toks;
   int c, h, w;
   AE_TRY(tokenize(spec, &c, &h, &w, &toks));
+  if (toks.empty()) return fail(AE_ESPEC, "layer spec has no layers");
   plan->batch = batch; plan->dtype = dtype; plan->bn_mode = bn_mode;
+  if (!tensor_fits(batch, c, h, w)) return fail(AE_ESHAPE, "the input tensor of the batch exceeds 2 GiB");
   plan->c0 = c; plan->h0 = h; plan->w0 = w;
   plan->steps.clear();
   int64_t off = 0;
@@ -146,6 +167,9 @@ int build_plan(const char* spec, int batch, int dtype, int bn_mode, Plan* plan) 
         st.k = cv.a;
       }
       st.cout = cv.b;
+      if (!tensor_fits(batch, std::max(st.cin, st.cout), (int64_t)h << st.up, (int64_t)w << st.up) ||
+          !tensor_fits(1, st.cout, st.cin, st.k * st.k))
+        return fail(AE_ESHAPE, "token %d: an activation or weight tensor of this layer exceeds 2 GiB", (int)j);
       st.hc = h << st.up; st.wc = w << st.up;
       st.w_off = off;
       off += (int64_t)st.cout * st.cin * st.k * st.k;
@@ -181,7 +205,8 @@ int build_plan(const char* spec, int batch, int dtype, int bn_mode, Plan* plan) 
       ++i;
     } else if (t.kind == T_RESHAPE) {
       if (h != 1 || w != 1) return fail(AE_ESPEC, "reshape needs a flattened input");
-      if ((int64_t)t.a * t.b * t.c != (int64_t)c) return fail(AE_ESHAPE, "reshape changes the element count");
+      if (!tensor_fits(batch, t.a, t.b, t.c) || (int64_t)t.a * t.b * t.c != (int64_t)c)
+        return fail(AE_ESHAPE, "reshape changes the element count");
       if (t.a > 1 && t.b * t.c > 1) add_transpose(t.a, t.b * t.c, (int)i, t.a, t.b, t.c);
       else if (!plan->steps.empty()) plan->steps.back().last_token = (int)i;
       c = t.a; h = t.b; w = t.c;

@@ -1,5 +1,8 @@
 """Helpers of the GPU parity tests: run the same seeded case through the HIP library
 (via its C boundary) and through the CPU oracle, and compare tensor by tensor."""
+import json
+import os
+
 import numpy as np
 
 import oracle.ae_oracle as orc
@@ -59,7 +62,17 @@ def rel_errors(a, o):
     return float(l2), float(lm)
 
 
-STRICT = True   # set False (debugging only) to collect errors instead of asserting
+STRICT = os.environ.get("AE_PARITY_NONSTRICT", "") == ""   # unset (debugging only) to collect errors instead of asserting
+REPORT = os.environ.get("AE_PARITY_REPORT", "")              # a file that receives one JSON line per case (measurements)
+
+# Gradients of networks whose ReLU masks / max-pool winners differ between the two sides.  The decisions are
+# COUNTED (count_flips below: the device's saved tensors against the oracle's, nothing is fed from one side to the
+# other) and every gradient tensor of a layer in step s is held to
+#     relative L2 error  <=  base tolerance  +  FLIP_C * sqrt( sum over steps t >= s of flipped fraction f_t ):
+# a flipped decision in step t >= s replaces one term of the gradient signal that reaches layer s by another of
+# typical size (relative change sqrt(f_t) in L2, independent between steps); FLIP_C = 2 covers the spread of the
+# flipped terms' magnitudes around the typical one.  No flips at or behind a layer => the plain 1e-4 / 2e-2 bar.
+FLIP_C = 2.0
 
 
 def assert_close(a, o, tol, what, tol_max=None):
@@ -75,8 +88,56 @@ def to_dev(a, dtype, torch):
     return t.to(torch.bfloat16).contiguous() if dtype == "bf16" else t
 
 
+def _winners(a):
+    """Index (scan order (0,0),(0,1),(1,0),(1,1), first maximum) of the largest value in every 2x2 window of a [B][C][H][W] array."""
+    b, c, h, w = a.shape
+    return a.reshape(b, c, h // 2, 2, w // 2, 2).transpose(0, 1, 2, 4, 3, 5).reshape(b, c, h // 2, w // 2, 4).argmax(axis=-1)
+
+
+def count_flips(m, net, params, batch):
+    """Fraction, per step of the device's plan, of the discrete decisions of the backward pass (ReLU mask bits,
+    max-pool winners) on which the device's saved tensors and the oracle's disagree.  Test-side bookkeeping only:
+    neither side sees the other's values."""
+    import torch
+    flips, prev = {}, -1
+    for s in range(m.model_num_steps()):
+        tok, chw = m.model_step_info(s)
+        first, prev = prev + 1, tok
+        kinds = [net.ops[i + 1]["kind"] for i in range(first, tok + 1)]
+        if "relu" not in kinds and "pool2" not in kinds:
+            continue
+        buf = torch.empty((batch,) + chw, dtype=torch.float32, device="cuda")
+        m.model_get_activation(s, buf)
+        out_d = buf.cpu().numpy()
+        del buf
+        out_o = net.activation(tok).reshape(out_d.shape)
+        if "pool2" in kinds:
+            ipool = first + kinds.index("pool2")
+            cshape = m.model_get_conv_output(s)
+            raw = torch.empty((batch,) + cshape, dtype=torch.float32, device="cuda")
+            m.model_get_conv_output(s, raw)
+            raw_d = raw.cpu().numpy()
+            del raw
+            if "bn" in kinds:       # batch-norm keeps the order of a channel's values if gamma > 0 and reverses it if gamma < 0
+                off = net.ops[first + kinds.index("bn") + 1]["param_off"]
+                raw_d *= np.sign(params[off:off + cshape[0]]).astype(np.float32)[None, :, None, None]
+            w_d = _winners(raw_d)
+            del raw_d
+            w_o = _winners(net.activation(ipool - 1).reshape((batch,) + cshape))
+            if "relu" in kinds:
+                a_d, a_o = out_d > 0, out_o > 0
+                flip = (a_d != a_o) | (a_d & a_o & (w_d != w_o))
+            else:
+                flip = w_d != w_o
+        else:
+            flip = (out_d > 0) != (out_o > 0)
+        flips[s] = float(flip.mean())
+    return flips
+
+
 def run_case(spec, batch, dtype="f32", seed=0, snr_db=10.0, first_sample=0, bn_mode=0, backward=True,
-             perturb=True, check_acts=True, x=None, params=None, cot=None, grad_tol=None, grad_cos=None):
+             perturb=True, check_acts=True, x=None, params=None, cot=None, grad_tol=None, grad_cos=None,
+             flips=False, tag=None):
     """Run spec on both sides; assert parity of y, every saved activation and (optionally)
     every gradient.  Returns a dict of the worst errors.
 
@@ -84,8 +145,10 @@ def run_case(spec, batch, dtype="f32", seed=0, snr_db=10.0, first_sample=0, bn_m
     bf16 models: y and activations against the plain (real-number) oracle at 2e-2, and again
     against the oracle emulating the bfloat16 storage format; gradients against the emulating
     oracle, so that ReLU masks and max-pool winners are decided in the format's precision on
-    both sides.  grad_tol / grad_cos override the gradient bar (deep bf16 networks: see
-    DEEP_BF16_GRAD)."""
+    both sides.  grad_tol / grad_cos override the gradient bar.  flips=True: the decisions on which
+    the two sides differ are counted and the gradient bar of each layer follows from the count (FLIP_C).
+    cot="mse": the upstream gradient is that of the mean squared error against the input, from the oracle's
+    output (what a training step feeds the backward pass)."""
     import torch
     from paper_2602_17681_amd import binding as ae
 
@@ -129,7 +192,24 @@ def run_case(spec, batch, dtype="f32", seed=0, snr_db=10.0, first_sample=0, bn_m
                 atol = TOL_ACT_PLAIN[dtype] if rname == "plain" else tol
                 worst["act%d/%s" % (s, rname)] = assert_close(
                     got, ref, atol, "activation of step %d (token %d) vs %s oracle" % (s, tok, rname), tol_max=tolm)
+    step_of_op, cum = {}, {}
+    if backward and flips:
+        fl = count_flips(m, net, params, batch)
+        worst["flips"] = fl
+        prev, tot = -1, 0.0
+        ns = m.model_num_steps()
+        toks = [m.model_step_info(s)[0] for s in range(ns)]
+        for s in range(ns - 1, -1, -1):
+            tot += fl.get(s, 0.0)
+            cum[s] = tot
+        for s in range(ns):
+            for op in range(prev + 1, toks[s] + 1):
+                step_of_op[op] = s
+            prev = toks[s]
     if backward:
+        if isinstance(cot, str) and cot == "mse":
+            _, dmse = orc.loss_mse(y_refs[-1], x.astype(np.float64))
+            cot = wl.round_to_bf16(dmse.astype(np.float32)) if bf else dmse.astype(np.float32)
         if cot is None:
             cot = wl.make_cotangent((batch,) + m.out_shape, seed, bf16=bf)
         g_ref, _ = net.backward(params, cot.astype(np.float64))
@@ -154,6 +234,10 @@ def run_case(spec, batch, dtype="f32", seed=0, snr_db=10.0, first_sample=0, bn_m
                 if STRICT:
                     assert np.abs(g[sl]).max() <= max(gtol, 1e-3) * scale * 10, name
                 continue
+            if flips:
+                bound = gtol + FLIP_C * float(np.sqrt(cum[step_of_op[e["op"]]]))
+                worst[name] = assert_close(g[sl], g_ref[sl], bound, name, tol_max=max(tolm, 3 * bound)) + (bound,)
+                continue
             worst[name] = assert_close(g[sl], g_ref[sl], gtol, name, tol_max=max(2 * gtol, 5e-2) if grad_cos is not None else max(gtol, tolm))
             if grad_cos is not None and sz >= 16:
                 c = float(np.dot(g[sl], g_ref[sl]) / (np.linalg.norm(g[sl]) * np.linalg.norm(g_ref[sl])))
@@ -161,6 +245,9 @@ def run_case(spec, batch, dtype="f32", seed=0, snr_db=10.0, first_sample=0, bn_m
                 if STRICT:
                     assert c >= grad_cos, "%s: cosine %.4f < %.4f" % (name, c, grad_cos)
     m.close()
+    if REPORT:
+        with open(REPORT, "a") as f:
+            f.write(json.dumps(dict(case=tag or spec, batch=batch, dtype=dtype, worst={k: v for k, v in worst.items()})) + "\n")
     return worst
 
 

@@ -35,7 +35,7 @@ def _rt(a, dtype):
 
 def _side(n, seed, dtype):
     """A well-conditioned n x n matrix, its inverse (of the stored matrix, then stored) and a shift."""
-    a, v, ainv, _ = wl.make_transform(n, seed=seed, bf16=(dtype == "bf16"), kind="affine")
+    a, v, ainv = wl.make_transform(n, seed=seed, bf16=(dtype == "bf16"), kind="affine")
     return a.astype(np.float64), ainv.astype(np.float64), v.astype(np.float64)
 
 

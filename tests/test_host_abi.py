@@ -49,7 +49,10 @@ def test_describe_matches_walker_and_oracle(ae):
     ("", -2), ("conv3:4", -2), ("in:3x4", -2), ("in:3x4x4,conv5:2", -2), ("in:3x5x5,conv3:2,pool2", -3),
     ("in:3x4x4,fc:5", -3), ("in:3x4x4,flatten,reshape:3x4x5", -3), ("in:3x4x4,conv3:0", -2), ("in:3x4x4,,relu", -2),
     ("in:3x4x4,foo", -2), ("in:3x4x4,relu", -2), ("in:3x4x4,up2,relu", -2), ("in:3x4x4,conv3:4,pool2,bn", -2),
-    ("in:3x4x4,conv3:4x", -2), ("in:3x4x4,reshape:3x4x4", -2)])
+    ("in:3x4x4,conv3:4x", -2), ("in:3x4x4,reshape:3x4x4", -2),
+    # sizes that would overflow 32-bit arithmetic in the planner: refused before any step is built
+    ("in:1x65536x65536,flatten,fc:8", -3), ("in:1x1x1,fc:8,reshape:65536x65536x1", -3), ("in:4x4x4,conv3:999999999", -3),
+    ("in:4x4x4,conv3:9999999999", -2), ("in:999999999x999999999x999999999,conv3:4", -3), ("in:3x4x4", -2)])
 def test_bad_specs(ae, bad, code):
     with pytest.raises(ae.AeError) as e:
         ae.model_describe(bad, 2)

@@ -191,8 +191,9 @@ def make_activations(rows, d, seed, bf16=False):
 
 
 def make_transform(d, seed, bf16=False, kind="affine"):
-    """An invertible d x d matrix A, a shift v, A^-1 and -A^-1 v for the transformation-error path (float32
-    arrays; the inverse is taken in float64 of the matrix AS STORED, then stored in the same type).
+    """An invertible d x d matrix A, a shift v and A^-1 for the transformation-error path (float32 arrays; the
+    inverse is taken in float64 of the matrix AS STORED, then stored in the same type).  The constant term of the
+    inverse map is the method's own arithmetic and is formed by each side for itself.
     kind: "identity", "hadamard" (orthonormal Walsh-Hadamard, d a power of two), "affine" (a random
     rotation times per-channel gains in [0.5, 2], plus a dense perturbation, with a shift)."""
     rng = np.random.default_rng([seed, 0x7A4F])
@@ -215,9 +216,7 @@ def make_transform(d, seed, bf16=False, kind="affine"):
     ainv = np.linalg.inv(a.astype(np.float64)).astype(np.float32)
     if bf16:
         ainv = round_to_bf16(ainv)
-    v = v.astype(np.float32)
-    inv_shift = (-(ainv.astype(np.float64) @ v.astype(np.float64))).astype(np.float32)
-    return a, v, ainv, inv_shift
+    return a, v.astype(np.float32), ainv
 
 
 def make_lu_params(d, seed, kind="random", noise=0.0, block=32):
