@@ -225,6 +225,17 @@ int model_transform_mse_elem(const void* x, const void* a_mat, const float* v, c
                              int64_t rows, int64_t d, int block, int elem, int dtype, void* yq, void* workspace,
                              float* e_blocks, float* e_total, void* stream);
 
+/* model_transform_mse_elem for callers that cannot allocate device memory or bring a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, definitions and results, but the
+ * per-tile partial sums live in a 4 MiB buffer built into the library's device code (each GPU the library runs on
+ * holds its own copy until the process ends; its address is looked up on the first call on that device).  The call
+ * allocates nothing.  Shapes whose model_transform_mse_workspace exceeds 4 MiB (rows/256 * d > 524 288 for bf16,
+ * rows/128 * d for fp32) are AE_EINVAL.  All calls on one GPU share the buffer: calls that overlap in time on one GPU
+ * (two streams, two threads) race; calls ordered on one stream do not. */
+int model_transform_mse_static(const void* x, const void* a_mat, const float* v, const void* a_inv, const float* inv_shift,
+                               int64_t rows, int64_t d, int block, int elem, int dtype, void* yq, float* e_blocks,
+                               float* e_total, void* stream);
+
 /* LU parametrisation of a learnable invertible matrix (the paper's Section on learning affine transformations,
  * Eq. 4):  A = P L (U + diag(s)).  Free parameters (device pointers, binary32 master copies): lp, up [d][d]
  * row-major, of which only the strictly lower part of lp and the strictly upper part of up are read (L has a

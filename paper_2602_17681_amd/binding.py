@@ -23,7 +23,7 @@ SYMBOLS = [
     "model_set_sample_offset", "model_forward", "model_backward", "model_loss_mse", "model_noise",
     "model_pnorm_awgn", "model_gen_bits", "model_count_errors", "model_num_steps", "model_step_info",
     "model_get_activation", "model_get_conv_output", "model_timing_enable", "model_set_overlap", "model_calibrate_mfma", "model_mx_quantize", "model_mx_quantize_elem", "model_transform_mse_workspace",
-    "model_transform_mse", "model_transform_mse_elem", "model_inverse_shift", "model_lu_workspace", "model_lu_compose", "model_lu_backward", "model_vol_penalty", "model_lu_inverse_workspace", "model_lu_inverse", "model_lu_compose_batch", "model_lu_backward_batch", "model_lu_inverse_batch", "model_lu_timing", "model_qr_workspace", "model_qr_compose", "model_qr_backward", "model_qr_inverse", "model_fold_workspace", "model_fold_linear", "model_fold_embedding", "model_timing_slots",
+    "model_transform_mse", "model_transform_mse_elem", "model_transform_mse_static", "model_inverse_shift", "model_lu_workspace", "model_lu_compose", "model_lu_backward", "model_vol_penalty", "model_lu_inverse_workspace", "model_lu_inverse", "model_lu_compose_batch", "model_lu_backward_batch", "model_lu_inverse_batch", "model_lu_timing", "model_qr_workspace", "model_qr_compose", "model_qr_backward", "model_qr_inverse", "model_fold_workspace", "model_fold_linear", "model_fold_embedding", "model_timing_slots",
     "model_timing_read", "model_timing_reset", "model_last_error",
 ]
 
@@ -66,6 +66,7 @@ def _load():
     L.model_transform_mse_workspace.argtypes = [C.c_int64, C.c_int64, C.c_int, i64p]
     L.model_transform_mse.argtypes = [vp, vp, vp, vp, vp, C.c_int64, C.c_int64, C.c_int, C.c_int, vp, vp, vp, vp, vp]
     L.model_transform_mse_elem.argtypes = [vp, vp, vp, vp, vp, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp, vp]
+    L.model_transform_mse_static.argtypes = [vp, vp, vp, vp, vp, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp]
     L.model_inverse_shift.argtypes = [vp, vp, C.c_int64, C.c_int, vp, vp]
     L.model_lu_workspace.argtypes = [C.c_int64, C.c_int, i64p]
     L.model_lu_compose.argtypes = [vp, vp, vp, vp, vp, C.c_int64, C.c_int, vp, vp, vp]
@@ -287,6 +288,16 @@ def model_inverse_shift(a_inv, v, d, inv_shift):
     dtype = AE_BF16 if a_inv.dtype == torch.bfloat16 else AE_F32
     assert a_inv.numel() == d * d and v.numel() == d and inv_shift.numel() == d
     _check(lib.model_inverse_shift(_ptr(a_inv), _ptr(v, torch.float32), d, dtype, _ptr(inv_shift, torch.float32), _stream()))
+
+
+def model_transform_mse_static(x, a_mat, v, a_inv, inv_shift, rows, d, block, yq, e_blocks, e_total, elem="fp4"):
+    dtype = AE_BF16 if x.dtype == torch.bfloat16 else AE_F32
+    assert x.numel() == rows * d and yq.numel() == rows * d and a_mat.numel() == d * d and a_inv.numel() == d * d
+    assert a_mat.dtype == x.dtype and a_inv.dtype == x.dtype and yq.dtype == x.dtype
+    assert v.numel() == d and inv_shift.numel() == d and e_blocks.numel() == d // block and e_total.numel() == 1
+    _check(lib.model_transform_mse_static(_ptr(x), _ptr(a_mat), _ptr(v, torch.float32), _ptr(a_inv), _ptr(inv_shift, torch.float32),
+                                          rows, d, block, MX_ELEMS[elem], dtype, _ptr(yq), _ptr(e_blocks, torch.float32),
+                                          _ptr(e_total, torch.float32), _stream()))
 
 
 def model_lu_workspace(d, dtype):

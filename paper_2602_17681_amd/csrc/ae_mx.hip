@@ -11,6 +11,8 @@
 #include <hip/hip_runtime.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "ae_device.h"
 #include "ae_internal.h"
 
@@ -115,6 +117,30 @@ __global__ void k_mse_total(const float* __restrict__ eb, int nb, float* __restr
   if (threadIdx.x == 0) *e = (float)(acc / (double)nb);
 }
 
+// Scratch of model_transform_mse_static: the per-tile column sums the residual epilogue hands to k_mse_blocks,
+// in device memory the code object itself carries (no allocation at run time).  Every device the library
+// runs on holds its own copy at its own address; the address is looked up once per device.
+constexpr int64_t kStaticScratchBytes = 4 << 20;
+static __device__ __align__(256) float g_static_scratch[kStaticScratchBytes / 4];
+constexpr int kMaxDevices = 64;
+float* g_static_scratch_ptr[kMaxDevices];      // per device, filled on that device's first call
+std::mutex g_static_scratch_mutex;
+
+int static_scratch(float** out) {
+  int dev = -1;
+  AE_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(AE_EHIP, "model_transform_mse_static: device index %d not supported", dev);
+  std::lock_guard<std::mutex> lock(g_static_scratch_mutex);
+  if (!g_static_scratch_ptr[dev]) {
+    float* ptr = nullptr;
+    AE_HIP(hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(g_static_scratch)));
+    if (!ptr) return fail(AE_EHIP, "model_transform_mse_static: the scratch array has no device address");
+    g_static_scratch_ptr[dev] = ptr;
+  }
+  *out = g_static_scratch_ptr[dev];
+  return AE_OK;
+}
+
 // The constant term of the inverse map of Definition 3.1, T^-1(y) = A^-1 y - A^-1 v:  out[i] = -sum_j ainv[i][j] v[j].
 // One wavefront per row; products and sums in double (d of them per row: nothing to gain from less).
 template <typename T>
@@ -208,6 +234,21 @@ extern "C" int model_inverse_shift(const void* a_inv, const float* v, int64_t d,
   else
     hipLaunchKernelGGL(k_inverse_shift<float>, dim3(blocks), dim3(NT), 0, (hipStream_t)stream, (const float*)a_inv, v, (int)d, inv_shift);
   return launch_status("inverse_shift");
+}
+
+extern "C" int model_transform_mse_static(const void* x, const void* a_mat, const float* v, const void* a_inv,
+                                          const float* inv_shift, int64_t rows, int64_t d, int block, int elem, int dtype,
+                                          void* yq, float* e_blocks, float* e_total, void* stream) {
+  using namespace ae;
+  int64_t need = 0;
+  AE_TRY(model_transform_mse_workspace(rows, d, dtype, &need));
+  if (need > kStaticScratchBytes)
+    return fail(AE_EINVAL, "model_transform_mse_static: this shape needs %lld bytes of scratch, the built-in buffer holds %lld "
+                "(use model_transform_mse with a workspace of your own)", (long long)need, (long long)kStaticScratchBytes);
+  float* scratch = nullptr;
+  AE_TRY(static_scratch(&scratch));
+  // every float of the scratch that k_mse_blocks reads is written by the second product's epilogue first: nothing to clear
+  return model_transform_mse_elem(x, a_mat, v, a_inv, inv_shift, rows, d, block, elem, dtype, yq, scratch, e_blocks, e_total, stream);
 }
 
 extern "C" int model_mx_quantize_elem(const void* x, void* q, int64_t rows, int64_t d, int block, int elem, int dtype, void* stream) {
