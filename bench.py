@@ -19,10 +19,11 @@ import workloads as wl
 
 PEAK = {"bf16": 2500.0, "f32": 157.3}     # dense MFMA TFLOP/s, MI355X
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch (fetched + written) of a kernel family, measured with rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE on this workload and scaled by the same counters of a plain 256 MiB copy (fetch x2.000,
-# write x1.000); commands and per-kernel table: profiles/cfg5_hbm_traffic.md.  Unmeasured: None.
-TRAFFIC_BYTES_PER_LAUNCH = {"cfg5": {"k_igemm": 85.5e6, "k_wgrad": 74.8e6}}
+# HBM bytes per launch (fetched + written) of a kernel family, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# summarised in the named file under profiles/ (each counter scaled by what it reads for a plain 256 MiB copy: fetch
+# x2.000, write x1.000).  A figure belongs to the kernels as they were when its profile was taken: an entry is removed
+# (traffic = null in the JSON line) when the kernels of its family change, until the counters are collected again.
+TRAFFIC = {}
 
 
 def build_case(name, torch, ae, batch=None):
@@ -50,7 +51,7 @@ def build_case(name, torch, ae, batch=None):
 
 def one_step(st, ae):
     cfg, m = st["cfg"], st["m"]
-    snr = cfg["snr_db"][st["i"] % len(cfg["snr_db"])]
+    snr = st.get("snr", cfg["snr_db"][0])          # one SNR point per timed block (run_timed is called per point)
     if st["name"] == "cfg4":
         first = st["i"] * st["B"]
         ae.model_gen_bits(cfg["seed"], first, st["B"], m.in_shape[0], st["x"])
@@ -105,10 +106,38 @@ FAMILY = {"conv_mfma": "k_igemm", "dgrad_mfma": "k_igemm", "conv_mfma_phases": "
 EXECUTED_SHARE = {"conv_mfma_phases": 4.0 / 9.0, "dgrad_mfma_stride2": 4.0 / 9.0}
 
 
-def roofline_of(rows, dtype, workload=None):
-    """The kernel that takes the largest share of the step (all its launches together), priced
-    against the roof that bounds it: total algorithmic FLOPs (or bytes) of its launches divided by
-    their total HIP-event time, i.e. per-launch average work over per-launch average duration."""
+_MEASURED = {}
+
+
+def measured_peaks(ae):
+    """What plain loops reach on THIS device in this run, beside the nominal peaks: independent 32x32x16 bf16
+    matrix-core instructions on every compute unit (operands all 1.0; random operands with the LDS fragment reads of a
+    128x64 wave tile, the ceiling of a real K loop under this chip's power management), and a 256 MiB device copy."""
+    if _MEASURED:
+        return _MEASURED
+    import torch
+    _MEASURED["mfma_bf16_ones_tflops"] = round(max(ae.model_calibrate_mfma(0, 0, iters=20000)[0] for _ in range(2)), 1)
+    _MEASURED["mfma_bf16_random_with_lds_reads_tflops"] = round(max(ae.model_calibrate_mfma(6, 1, iters=20000)[0] for _ in range(2)), 1)
+    src = torch.ones(256 << 20, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(2):
+        dst.copy_(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    _MEASURED["hbm_copy_read_plus_write_gbs"] = round(2.0 * (256 << 20) * 5 / e0.elapsed_time(e1) / 1e6, 1)
+    return _MEASURED
+
+
+def roofline_of(rows, dtype, workload=None, ae=None):
+    """The kernel family that takes the largest share of the step (all its launches together), priced against the
+    roof that bounds it: work of its launches divided by their total HIP-event time.  For a matrix-core family
+    `achieved` / `frac` count the multiply-adds the kernels EXECUTE (what the hardware roof bounds);
+    `achieved_algorithmic` counts the FLOPs of the layers' definition (2*M*N*K), which is larger where a layer runs in
+    a cheaper algebraic form; their ratio is the saving of those forms, not utilisation."""
     if not rows:
         return None
     fam = {}
@@ -123,18 +152,19 @@ def roofline_of(rows, dtype, workload=None):
     name, top = max(fam.items(), key=lambda kv: kv[1]["ms"])
     avg_ms = top["ms"] / top["launches"]
     balance = PEAK[dtype] * 1e12 / (HBM_PEAK_GBS * 1e9)
+    tr = TRAFFIC.get(workload, {}).get(name)
+    common = dict(traffic=None if tr is None else tr["bytes_per_launch"], traffic_source=None if tr is None else tr["source"],
+                  avg_ms=avg_ms, launches_per_step=top["launches"], bytes_per_launch=top["bytes"] / top["launches"],
+                  peak_measured=measured_peaks(ae) if ae is not None else None)
     if top["flops"] > 0 and top["flops"] / max(top["bytes"], 1.0) >= balance:
         ach = top["flops"] / top["ms"] / 1e9
         ach_exec = top["flops_exec"] / top["ms"] / 1e9
-        return dict(bound="mfma", kernel=name, achieved=ach, peak=PEAK[dtype], unit="TFLOP/s", frac=ach / PEAK[dtype],
-                    achieved_executed=ach_exec, frac_executed=ach_exec / PEAK[dtype],
-                    traffic=TRAFFIC_BYTES_PER_LAUNCH.get(workload, {}).get(name), avg_ms=avg_ms,
-                    launches_per_step=top["launches"], flops_per_launch=top["flops"] / top["launches"],
-                    bytes_per_launch=top["bytes"] / top["launches"])
+        return dict(bound="mfma", kernel=name, achieved=ach_exec, peak=PEAK[dtype], unit="TFLOP/s", frac=ach_exec / PEAK[dtype],
+                    achieved_algorithmic=ach, frac_algorithmic=ach / PEAK[dtype],
+                    flops_per_launch=top["flops_exec"] / top["launches"],
+                    flops_per_launch_algorithmic=top["flops"] / top["launches"], **common)
     ach = top["bytes"] / top["ms"] / 1e6
-    return dict(bound="hbm", kernel=name, achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS,
-                traffic=TRAFFIC_BYTES_PER_LAUNCH.get(workload, {}).get(name), avg_ms=avg_ms,
-                launches_per_step=top["launches"], bytes_per_launch=top["bytes"] / top["launches"])
+    return dict(bound="hbm", kernel=name, achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS, **common)
 
 
 # measured HBM bytes per launch of k_mx_quantize on this workload (profiles/mx_quantize.md): FETCH_SIZE x2.000 + WRITE_SIZE
@@ -555,12 +585,72 @@ def bench_qr_param(torch, ae, args):
     }
 
 
-def cpu_baseline(name, budget_s=20.0):
+def bench_monte_carlo(torch, ae, args):
+    """cfg4 end to end: the error-rate estimate over ALL 1e8 samples at each of the four SNR points — 1 525 launches of
+    65 536 samples and one of 57 600 (a second handle) per point through model_monte_carlo, the two 64-bit counters
+    zeroed once before and read once after each point.  value = samples/s over the whole run."""
+    cfg = wl.CONFIGS["cfg4"]
+    B, total, K = cfg["batch"], int(args.mc_samples or cfg["total_samples"]), 64
+    m = ae.Model(cfg["spec"], B)
+    tail = ae.Model(cfg["spec"], total % B) if total % B else None
+    params = torch.from_numpy(wl.make_params(cfg["spec"], cfg["seed"])).cuda()
+    for h in (m, tail):
+        if h is not None:
+            h.model_set_params_static(True)           # the parameters do not change between the launches of a run
+    x = torch.empty((B, K), device="cuda")
+    y = torch.empty((B, K), device="cuda")
+    be = torch.zeros(1, dtype=torch.int64, device="cuda")
+    ke = torch.zeros(1, dtype=torch.int64, device="cuda")
+    ae.model_monte_carlo(m, tail, params, 0.0, cfg["seed"], 0, min(total, 2 * B + total % B), x, y, be, ke)   # warm-up
+    torch.cuda.synchronize()
+    per_snr, t_all = [], 0.0
+    for snr in cfg["snr_db"]:
+        be.zero_()
+        ke.zero_()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ae.model_monte_carlo(m, tail, params, snr, cfg["seed"], 0, total, x, y, be, ke)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        t_all += dt
+        nb, nk = int(be.item()), int(ke.item())      # the one read-back of the point
+        per_snr.append(dict(snr_db=snr, seconds=round(dt, 4), samples_per_s=total / dt, bit_errors=nb, block_errors=nk,
+                            ber=nb / (K * total), bler=nk / total))
+    launches = total // B + (1 if total % B else 0)
+    # per-kernel durations of the launch (HIP events on the stream the kernels run on): a separate short pass
+    st = build_case("cfg4", torch, ae)
+    st["m"].model_set_params_static(True)
+    run_timed(st, ae, torch, 3, 2)
+    run_timed(st, ae, torch, args.steps, 0, timing=True)
+    rows = kernel_table(st, args.steps)
+    st["m"].close()
+    out = {
+        "metric": "samples/sec, forward (Monte-Carlo error-rate estimate, all launches)", "value": len(per_snr) * total / t_all,
+        "unit": "samples/s", "n_gpus": 1, "steps": launches * len(per_snr), "warmup": 3,
+        "ms_per_step": t_all / (launches * len(per_snr)) * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "cfg4 full run: %s" % cfg["spec"], "batch": B, "total_samples_per_snr": total,
+                   "launches_per_snr": launches, "tail_launch": total % B, "snr_db": cfg["snr_db"], "seed": cfg["seed"],
+                   "pass": "message bits + forward + error count"},
+        "per_snr": per_snr,
+        "roofline": roofline_of(rows, "f32", "cfg4", ae),
+    }
+    if not args.no_cpu_baseline:
+        cb = cpu_baseline("cfg4")
+        cb["extrapolated_seconds_per_1e8_samples"] = total / cb["value"]
+        out["cpu_baseline"] = cb
+    return out
+
+
+def cpu_baseline(name, threads=None, sample=None):
     """The oracle as it stands, on a bounded sample of the same workload (same layer list and
-    resolution, smaller batch), timed on this machine's host cores."""
+    resolution, smaller batch), timed on this machine's host cores (threads: limit its OpenMP threads)."""
     import oracle.ae_oracle as orc
     cfg = wl.CONFIGS[name]
-    sample = {"cfg1": 8192, "cfg2": 256, "cfg3": 16, "cfg4": 131072, "cfg5": 8}[name]   # 10-30 s of host work
+    sample = sample or {"cfg1": 8192, "cfg2": 256, "cfg3": 16, "cfg4": 131072, "cfg5": 8}[name]   # 10-30 s of host work
+    all_threads = orc.num_threads()
+    if threads:
+        orc.set_num_threads(threads)
     spec = cfg["spec"]
     bf = cfg["dtype"] == "bf16"
     params = wl.make_params(spec, cfg["seed"], bf16=bf)
@@ -577,7 +667,10 @@ def cpu_baseline(name, budget_s=20.0):
     elif name == "cfg4":
         orc.count_errors(y.reshape(sample, 64), x.reshape(sample, 64))
     dt = time.perf_counter() - t0
-    return dict(value=sample / dt, unit="samples/s", cores=orc.num_threads(), kind="oracle",
+    used = orc.num_threads()
+    if threads:
+        orc.set_num_threads(all_threads)
+    return dict(value=sample / dt, unit="samples/s", cores=used, kind="oracle",
                 sample="batch %d of %s (%s), one step in %.1f s" % (
                     sample, name, "forward+loss+backward" if cfg["backward"] else "forward", dt))
 
@@ -595,6 +688,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-per-config", action="store_true")
     ap.add_argument("--kernels", action="store_true", help="also print the per-kernel table to stderr")
+    ap.add_argument("--full-run", action="store_true",
+                    help="with --config cfg4: the whole Monte-Carlo estimate (1e8 samples at each SNR point: 1 525 launches "
+                         "of 65 536 and one of 57 600), BER / BLER and samples/s per SNR point")
+    ap.add_argument("--mc-samples", type=int, default=0, help="--full-run: samples per SNR point (default: the configuration's 1e8)")
     ap.add_argument("--no-overlap", action="store_true",
                     help="keep every kernel of the backward pass on one stream (for per-kernel profiles: with the "
                          "default two streams the weight-gradient kernels share the chip with other kernels)")
@@ -691,6 +788,11 @@ def main():
         return
 
     name = args.config
+    if args.full_run:
+        if name != "cfg4" or args.spec:
+            sys.exit("bench.py: --full-run is the Monte-Carlo run of --config cfg4")
+        print(json.dumps(bench_monte_carlo(torch, ae, args)))
+        return
     if args.spec:
         name = "custom"
         wl.CONFIGS[name] = dict(spec=args.spec, batch=args.batch, dtype=args.dtype, seed=7, snr_db=[10.0],
@@ -701,8 +803,16 @@ def main():
     st = build_case(name, torch, ae)
     if args.no_overlap:
         st["m"].model_set_overlap(False)
-    # timed region: exactly `steps` steps, no instrumentation
-    dt = run_timed(st, ae, torch, args.steps, args.warmup, timing=False)
+    # timed region: exactly `steps` steps, no instrumentation.  A configuration with several SNR points (cfg2, cfg4)
+    # runs them as separate blocks of `steps` steps each: every point is reported, `value` is the rate over all of them.
+    per_snr, dt = [], 0.0
+    for snr in cfg["snr_db"]:
+        st["snr"] = snr
+        d1 = run_timed(st, ae, torch, args.steps, args.warmup if not per_snr else 1, timing=False)
+        per_snr.append(dict(snr_db=snr, samples_per_s=st["B"] * args.steps / d1, ms_per_step=d1 / args.steps * 1e3))
+        dt += d1
+    dt /= len(per_snr)                                   # seconds per block of `steps` steps, averaged over the points
+    st["snr"] = cfg["snr_db"][0]
     value = st["B"] * args.steps / dt
     # the same `steps` steps again with a pair of HIP events around every launch, recorded on the
     # stream the kernels run on (the event records cost about 15 % of the step time, so the
@@ -725,7 +835,8 @@ def main():
         "config": {"workload": "%s: %s" % (name, cfg["spec"]), "batch": st["B"], "snr_db": cfg["snr_db"],
                    "seed": cfg["seed"], "pass": "forward+loss+backward" if cfg["backward"] else "forward",
                    "backward_streams": 1 if args.no_overlap else 2},
-        "roofline": roofline_of(rows, cfg["dtype"], name),
+        "per_snr": per_snr,
+        "roofline": roofline_of(rows, cfg["dtype"], name, ae),
         "kernels": [dict(name=r["name"], ms_per_step=round(r["ms_per_step"], 5),
                          tflops=None if r["tflops"] is None else round(r["tflops"], 2),
                          gbs=None if r["gbs"] is None else round(r["gbs"], 1))
@@ -746,6 +857,9 @@ def main():
             per[other] = dict(samples_per_s=s2["B"] * k2 / d2, ms_per_step=d2 / k2 * 1e3)
             s2["m"].close()
             del s2
+        if not args.no_cpu_baseline:
+            # the smallest configuration also against the oracle on ONE host thread (bounded sample)
+            per["cfg1"]["cpu_oracle_one_thread"] = cpu_baseline("cfg1", threads=1, sample=1024)
         out["per_config"] = per
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(name)

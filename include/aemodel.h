@@ -148,6 +148,20 @@ int model_gen_bits(uint64_t seed, uint64_t first_sample, int64_t batch, int k, f
 int model_count_errors(const float* y, const float* x_pm1, int64_t batch, int k, uint64_t* bit_err,
                        uint64_t* blk_err, void* stream);
 
+/* A whole Monte-Carlo error-rate estimate at one SNR point: the samples with global indices first_sample ..
+ * first_sample + total_samples - 1 run in launches of m's batch size, each launch being
+ * model_gen_bits -> model_forward -> model_count_errors with the launch's sample offset, so the result does not
+ * depend on how the range is cut into launches.  When total_samples is not a multiple of m's batch, the last,
+ * shorter launch runs on m_tail, a second handle of the same network created with exactly that remaining batch
+ * (NULL otherwise).  m must be a binary32 model from k symbols (in:kx1x1) to k soft bits.
+ *   params  : device, binary32[n_params]       x_buf, y_buf : device scratch, binary32 [m's batch][k] each
+ *   bit_err, blk_err : device 64-bit counters the caller zeroes before and reads after (they accumulate):
+ *   BER = bit_err / (k * total_samples), BLER = blk_err / total_samples.
+ * Everything is enqueued on `stream`; nothing is read back or synchronised. */
+int model_monte_carlo(ae_model* m, ae_model* m_tail, const void* params, float snr_db, uint64_t seed,
+                      uint64_t first_sample, uint64_t total_samples, float* x_buf, float* y_buf, uint64_t* bit_err,
+                      uint64_t* blk_err, void* stream);
+
 /* Introspection for tests.  The pipeline is executed as fused steps; step s has
  * one saved output tensor.  model_step_info reports, for step s, the index of the
  * LAST spec token (0-based, not counting "in:") folded into it and its output
@@ -177,6 +191,12 @@ int model_timing_enable(ae_model* m, int on);
  * behaviour while per-kernel timing is enabled, so that each measured duration belongs to
  * one kernel alone).  Results are identical either way. */
 int model_set_overlap(ae_model* m, int on);
+/* Every pass converts the binary32 parameter blob into the kernels' operand layouts (the blob may change between
+ * calls).  on = 1 is the caller's promise that the CONTENTS of params stay the same from call to call (repeated
+ * evaluation, Monte-Carlo launches): the conversion then runs only in the first forward and the first backward
+ * pass after this call, and again whenever a different params pointer is passed.  Call it again (on = 1) after
+ * changing the values in place, or with on = 0 to return to converting in every pass (the default). */
+int model_set_params_static(ae_model* m, int on);
 int model_timing_slots(const ae_model* m, int* n_slots);
 int model_timing_read(ae_model* m, int slot, char* name, int name_len, double* total_ms, int64_t* launches,
                       double* flops_per_launch, double* bytes_per_launch);

@@ -204,7 +204,10 @@ struct Net {
   // arithmetic in between stays in double.  This puts the discrete decisions that
   // depend on stored values (ReLU masks, max-pool winners) in the precision the format
   // prescribes, which is what a gradient comparison needs; without it the oracle is the
-  // plain real-number definition.
+  // plain real-number definition.  The backward pass follows the same rule: the gradient
+  // with respect to a stored tensor is itself a stored tensor of the format (the gradient
+  // a layer hands to the layer before it), so it is rounded to bfloat16 too; gradients
+  // with respect to parameters are not (they are returned in binary32 / double).
   int store_bf16 = 0;
   int c0 = 0, h0 = 0, w0 = 0;
   std::vector<Op> ops;
@@ -214,6 +217,13 @@ struct Net {
   std::vector<std::vector<double>> bn_mean, bn_invstd;  // per op (empty unless BN)
   std::vector<double> pn_r;                             // per-sample r of the (single) pnorm
   bool have_forward = false;
+  // Given decisions (oracle_set_decisions; empty = none).  A ReLU mask bit and a max-pool winner are discrete
+  // decisions on forward values; two correct implementations whose forward values differ by rounding disagree
+  // on a few of them, and the gradient is discontinuous there.  A test that wants to compare the ARITHMETIC of
+  // two backward passes can therefore state the decisions: per op, one byte per element of the op's OUTPUT —
+  // relu: 1 = the gradient passes; pool2: index 0..3 of the window element that receives the gradient, in the
+  // scan order (0,0),(0,1),(1,0),(1,1).  The backward definitions are otherwise unchanged.
+  std::vector<std::vector<uint8_t>> decisions;
 };
 
 bool parse_dims(const std::string& s, int* c, int* h, int* w) {
@@ -587,7 +597,7 @@ void bn_backward(const Op& o, int B, int mode, const float* prm, const std::vect
 }
 
 void pool_backward(const Op& o, int B, const std::vector<double>& x, const std::vector<double>& dy,
-                   std::vector<double>& dx) {
+                   std::vector<double>& dx, const std::vector<uint8_t>* given = nullptr) {
   const int C = o.cin, H = o.hin, W = o.win, Ho = o.hout, Wo = o.wout;
   dx.assign(x.size(), 0.0);
 #pragma omp parallel for schedule(static)
@@ -597,7 +607,7 @@ void pool_backward(const Op& o, int B, const std::vector<double>& x, const std::
         const double* px = &x[(size_t)nc * H * W];
         double v[4] = {px[(2 * i) * W + 2 * j], px[(2 * i) * W + 2 * j + 1], px[(2 * i + 1) * W + 2 * j],
                        px[(2 * i + 1) * W + 2 * j + 1]};
-        int a = pool_argmax(v);
+        int a = given ? ((*given)[((size_t)nc * Ho + i) * Wo + j] & 3) : pool_argmax(v);
         dx[(size_t)nc * H * W + (2 * i + a / 2) * W + 2 * j + (a & 1)] = dy[((size_t)nc * Ho + i) * Wo + j];
       }
 }
@@ -786,7 +796,10 @@ int oracle_backward(void* h, const float* params, const double* dy, double* grad
       case OP_BN: bn_backward(o, B, net->bn_mode, prm, in, net->bn_mean[ii], net->bn_invstd[ii], g, gprev, gp); break;
       case OP_RELU:  // derivative 0 for x <= 0
         gprev.resize(g.size());
-        for (size_t j = 0; j < g.size(); ++j) gprev[j] = in[j] > 0.0 ? g[j] : 0.0;
+        if (ii < net->decisions.size() && !net->decisions[ii].empty())
+          for (size_t j = 0; j < g.size(); ++j) gprev[j] = net->decisions[ii][j] ? g[j] : 0.0;
+        else
+          for (size_t j = 0; j < g.size(); ++j) gprev[j] = in[j] > 0.0 ? g[j] : 0.0;
         break;
       case OP_SIGMOID:  // s'(x) = s(x)(1-s(x)), evaluated from the op's input (the stored output may be rounded)
         gprev.resize(g.size());
@@ -795,16 +808,35 @@ int oracle_backward(void* h, const float* params, const double* dy, double* grad
           gprev[j] = g[j] * sg * (1.0 - sg);
         }
         break;
-      case OP_POOL2: pool_backward(o, B, in, g, gprev); break;
+      case OP_POOL2:
+        pool_backward(o, B, in, g, gprev, (ii < net->decisions.size() && !net->decisions[ii].empty()) ? &net->decisions[ii] : nullptr);
+        break;
       case OP_UP2: up_backward(o, B, g, gprev); break;
       case OP_FLATTEN:
       case OP_RESHAPE: gprev = g; break;
       case OP_PNORM: pnorm_backward(B, vol(o, false), out, net->pn_r, g, gprev); break;
       case OP_AWGN: gprev = g; break;  // additive noise: identity
     }
+    // storage-format emulation: gprev is the gradient w.r.t. this op's input, i.e. w.r.t. the output of op ii-1
+    if (net->store_bf16 && (ii == 0 || stored_output(*net, ii - 1)))
+      for (double& v : gprev) v = round_bf16(v);
     g.swap(gprev);
   }
   if (dx) std::memcpy(dx, g.data(), g.size() * sizeof(double));
+  return 0;
+}
+
+// State the decisions of op i (relu: pass bits; pool2: winner indices; n = elements of the op's output) for the
+// following oracle_backward calls; data = NULL withdraws them.  Returns 0, or -1 for a wrong op or size.
+int oracle_set_decisions(void* h, int i, const uint8_t* data, int64_t n) {
+  Net* net = (Net*)h;
+  if (i < 0 || i >= (int)net->ops.size()) return -1;
+  const Op& o = net->ops[i];
+  if (o.kind != OP_RELU && o.kind != OP_POOL2) return -1;
+  if (net->decisions.size() != net->ops.size()) net->decisions.assign(net->ops.size(), std::vector<uint8_t>());
+  if (!data) { net->decisions[i].clear(); return 0; }
+  if (n != (int64_t)net->batch * o.cout * o.hout * o.wout) return -1;
+  net->decisions[i].assign(data, data + n);
   return 0;
 }
 
@@ -817,6 +849,15 @@ double oracle_loss_mse(const double* y, const double* t, int64_t n, double* dy) 
     if (dy) dy[i] = 2.0 * d / (double)n;
   }
   return s / (double)n;
+}
+
+// Number of OpenMP threads the loops may use from now on (timing only: results do not depend on it).
+void oracle_set_num_threads(int n) {
+#ifdef _OPENMP
+  if (n > 0) omp_set_num_threads(n);
+#else
+  (void)n;
+#endif
 }
 
 int oracle_num_threads(void) {

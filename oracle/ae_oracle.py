@@ -50,9 +50,11 @@ def lib():
         L.oracle_get_activation.argtypes = [C.c_void_p, C.c_int, f64p]
         L.oracle_get_activation.restype = C.c_int64
         L.oracle_backward.argtypes = [C.c_void_p, f32p, f64p, f64p, f64p]
+        L.oracle_set_decisions.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_uint8), C.c_int64]
         L.oracle_loss_mse.argtypes = [f64p, f64p, C.c_int64, f64p]
         L.oracle_loss_mse.restype = C.c_double
         L.oracle_num_threads.restype = C.c_int
+        L.oracle_set_num_threads.argtypes = [C.c_int]
         _lib = L
     return _lib
 
@@ -125,6 +127,10 @@ def num_threads():
     return int(lib().oracle_num_threads())
 
 
+def set_num_threads(n):
+    lib().oracle_set_num_threads(int(n))
+
+
 OP_KINDS = ["conv", "bn", "relu", "sigmoid", "pool2", "up2", "flatten", "fc", "reshape", "pnorm", "awgn"]
 
 
@@ -177,6 +183,17 @@ class Net:
         assert out.size == n
         lib().oracle_get_activation(self._h, i, _p(out, C.c_double))
         return out
+
+    def set_decisions(self, i, data):
+        """State the discrete decisions of op i for the following backward() calls (relu: uint8 pass bits, pool2:
+        uint8 winner indices 0..3, shape of the op's output); data=None withdraws them."""
+        if data is None:
+            rc = lib().oracle_set_decisions(self._h, i, None, 0)
+        else:
+            d = np.ascontiguousarray(data, dtype=np.uint8)
+            rc = lib().oracle_set_decisions(self._h, i, _p(d, C.c_uint8), d.size)
+        if rc != 0:
+            raise ValueError("oracle: op %d takes no decisions of that size" % i)
 
     def backward(self, params, dy):
         p = _f32(params)

@@ -21,8 +21,8 @@ TORCH_DTYPE = {AE_F32: torch.float32, AE_BF16: torch.bfloat16}
 SYMBOLS = [
     "model_describe", "model_create", "model_destroy", "model_param_count", "model_io_shape",
     "model_set_sample_offset", "model_forward", "model_backward", "model_loss_mse", "model_noise",
-    "model_pnorm_awgn", "model_gen_bits", "model_count_errors", "model_num_steps", "model_step_info",
-    "model_get_activation", "model_get_conv_output", "model_timing_enable", "model_set_overlap", "model_calibrate_mfma", "model_mx_quantize", "model_mx_quantize_elem", "model_transform_mse_workspace",
+    "model_pnorm_awgn", "model_gen_bits", "model_count_errors", "model_monte_carlo", "model_num_steps", "model_step_info",
+    "model_get_activation", "model_get_conv_output", "model_timing_enable", "model_set_overlap", "model_set_params_static", "model_calibrate_mfma", "model_mx_quantize", "model_mx_quantize_elem", "model_transform_mse_workspace",
     "model_transform_mse", "model_transform_mse_elem", "model_transform_mse_static", "model_inverse_shift", "model_lu_workspace", "model_lu_compose", "model_lu_backward", "model_vol_penalty", "model_lu_inverse_workspace", "model_lu_inverse", "model_lu_compose_batch", "model_lu_backward_batch", "model_lu_inverse_batch", "model_lu_timing", "model_qr_workspace", "model_qr_compose", "model_qr_backward", "model_qr_inverse", "model_fold_workspace", "model_fold_linear", "model_fold_embedding", "model_timing_slots",
     "model_timing_read", "model_timing_reset", "model_last_error",
 ]
@@ -54,12 +54,14 @@ def _load():
     L.model_pnorm_awgn.argtypes = [vp, vp, C.c_int64, C.c_int64, C.c_int, C.c_float, C.c_uint64, C.c_uint64, vp]
     L.model_gen_bits.argtypes = [C.c_uint64, C.c_uint64, C.c_int64, C.c_int, vp, vp]
     L.model_count_errors.argtypes = [vp, vp, C.c_int64, C.c_int, vp, vp, vp]
+    L.model_monte_carlo.argtypes = [vp, vp, vp, C.c_float, C.c_uint64, C.c_uint64, C.c_uint64, vp, vp, vp, vp, vp]
     L.model_num_steps.argtypes = [vp, C.POINTER(C.c_int)]
     L.model_step_info.argtypes = [vp, C.c_int, C.POINTER(C.c_int), i64p]
     L.model_get_activation.argtypes = [vp, C.c_int, vp, vp]
     L.model_get_conv_output.argtypes = [vp, C.c_int, i64p, vp, vp]
     L.model_timing_enable.argtypes = [vp, C.c_int]
     L.model_set_overlap.argtypes = [vp, C.c_int]
+    L.model_set_params_static.argtypes = [vp, C.c_int]
     L.model_calibrate_mfma.argtypes = [C.c_int, C.c_int, C.c_int, vp, C.POINTER(C.c_double), C.POINTER(C.c_double), vp]
     L.model_mx_quantize.argtypes = [vp, vp, C.c_int64, C.c_int64, C.c_int, C.c_int, vp]
     L.model_mx_quantize_elem.argtypes = [vp, vp, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int, vp]
@@ -187,6 +189,9 @@ class Model:
 
     def model_set_overlap(self, on):
         _check(lib.model_set_overlap(self._h, 1 if on else 0))
+
+    def model_set_params_static(self, on):
+        _check(lib.model_set_params_static(self._h, 1 if on else 0))
 
     def model_timing_reset(self):
         _check(lib.model_timing_reset(self._h))
@@ -443,6 +448,15 @@ def model_calibrate_mfma(lds_reads, random_data=0, iters=4000):
     out, mhz = C.c_double(0.0), C.c_double(0.0)
     _check(lib.model_calibrate_mfma(lds_reads, random_data, iters, _ptr(scratch), C.byref(out), C.byref(mhz), _stream()))
     return out.value, mhz.value
+
+
+def model_monte_carlo(m, m_tail, params, snr_db, seed, first_sample, total_samples, x_buf, y_buf, bit_err, blk_err):
+    k = m.in_shape[0]
+    assert x_buf.numel() >= m.batch * k and y_buf.numel() >= m.batch * k and params.numel() == m.n_params
+    assert bit_err.dtype == torch.int64 and blk_err.dtype == torch.int64
+    _check(lib.model_monte_carlo(m._h, m_tail._h if m_tail is not None else C.c_void_p(0), _ptr(params, torch.float32), snr_db,
+                                 seed, first_sample, total_samples, _ptr(x_buf, torch.float32), _ptr(y_buf, torch.float32),
+                                 _ptr(bit_err), _ptr(blk_err), _stream()))
 
 
 def model_gen_bits(seed, first_sample, batch, k, x_pm1):

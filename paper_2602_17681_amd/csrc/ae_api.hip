@@ -61,6 +61,9 @@ struct ae_model {
   uint64_t first_sample = 0;
   bool have_forward = false;
   bool packed_in_batch = false;     // the current pass repacked all its weights with one launch
+  bool params_static = false;       // the caller promises unchanged parameters: repack only once per direction
+  const void* fwd_packed = nullptr; // parameter blob whose forward / input-gradient packing is still valid
+  const void* bwd_packed = nullptr;
 };
 
 using namespace ae;
@@ -306,15 +309,17 @@ int forward_conv(ae_model* m, int si, Step& st, const float* params, const void*
   if (st.has_bn) {
     const float* gb = params + st.bn_off;
     if (P.bn_mode == 0) {
+      const float* about = a.bias;    // the conv epilogues take their column statistics about the bias
       if (!a.partial) {
         TIMED(si, "fwd.col_stats", 0.0, raw_el * es, launch_col_stats(st.raw, rows, st.cout, P.dtype, m->partial, s));
         nblk = nblocks_for(rows);
+        about = nullptr;
       }
       TIMED(si, "fwd.bn_finalize", 0.0, (double)nblk * 2 * st.cout * 4,
-            launch_bn_finalize(m->partial, nblk, rows, st.cout, gb, nullptr, st.bn_vec, s));
+            launch_bn_finalize(m->partial, nblk, rows, st.cout, gb, nullptr, about, st.bn_vec, s));
     } else {
       TIMED(si, "fwd.bn_finalize", 0.0, 0.0,
-            launch_bn_finalize(nullptr, 0, rows, st.cout, gb, gb + 2 * st.cout, st.bn_vec, s));
+            launch_bn_finalize(nullptr, 0, rows, st.cout, gb, gb + 2 * st.cout, nullptr, st.bn_vec, s));
     }
   }
   if (second_pass)
@@ -594,6 +599,13 @@ int model_set_overlap(ae_model* m, int on) {
   return AE_OK;
 }
 
+int model_set_params_static(ae_model* m, int on) {
+  if (!m) return fail(AE_EINVAL, "model_set_params_static: null model");
+  m->params_static = on != 0;
+  m->fwd_packed = m->bwd_packed = nullptr;    // the next pass in each direction repacks
+  return AE_OK;
+}
+
 int model_timing_slots(const ae_model* m, int* n_slots) {
   if (!m || !n_slots) return fail(AE_EINVAL, "model_timing_slots: null argument");
   *n_slots = (int)m->slots.size();
@@ -665,7 +677,13 @@ int model_forward(ae_model* m, const void* params, const void* x, float snr_db, 
   m->have_forward = false;
   const size_t ns = P.steps.size();
   AE_TRY(join_pack(m, s, true));
-  AE_TRY(pack_all_beside(m, prm, false, s));
+  if (m->params_static && m->fwd_packed == params) {
+    m->packed_in_batch = true;     // the packed copies of an earlier call are still valid
+  } else {
+    AE_TRY(pack_all_beside(m, prm, false, s));
+    // valid for later calls only if this call packed every layer up front (not layer by layer on the way)
+    m->fwd_packed = (m->params_static && m->packed_in_batch) ? params : nullptr;
+  }
   for (size_t i = 0; i < ns; ++i) {
     Step& st = P.steps[i];
     const void* in = step_input(m, i, x);
@@ -715,7 +733,12 @@ int model_backward(ae_model* m, const void* params, const void* x, const void* d
   AE_TRY(join_side(m, 0, s));
   AE_TRY(join_side(m, 1, s));
   AE_TRY(join_pack(m, s, true));
-  AE_TRY(pack_all_beside(m, prm, true, s));
+  if (m->params_static && m->bwd_packed == params) {
+    m->packed_in_batch = true;
+  } else {
+    AE_TRY(pack_all_beside(m, prm, true, s));
+    m->bwd_packed = (m->params_static && m->packed_in_batch) ? params : nullptr;
+  }
   for (size_t ii = ns; ii-- > first_param;) {
     Step& st = P.steps[ii];
     void* gnext = (g == m->grad_a) ? m->grad_b : m->grad_a;
@@ -784,6 +807,40 @@ int model_count_errors(const float* y, const float* x_pm1, int64_t batch, int k,
   if (batch < 0 || k <= 0) return fail(AE_EINVAL, "model_count_errors: bad size");
   if (batch == 0) return AE_OK;
   return launch_count_errors(y, x_pm1, batch, k, bit_err, blk_err, (hipStream_t)stream);
+}
+
+// Monte-Carlo error-rate run: samples first_sample .. first_sample + total_samples - 1 in launches of m's batch,
+// the remainder (if any) on m_tail, whose batch must be exactly that remainder.  Per launch: message bits ->
+// forward -> error counts; everything is enqueued on `stream`, nothing is read back.
+int model_monte_carlo(ae_model* m, ae_model* m_tail, const void* params, float snr_db, uint64_t seed,
+                      uint64_t first_sample, uint64_t total_samples, float* x_buf, float* y_buf, uint64_t* bit_err,
+                      uint64_t* blk_err, void* stream) {
+  if (!m || !x_buf || !y_buf || !bit_err || !blk_err) return fail(AE_EINVAL, "model_monte_carlo: null argument");
+  const Plan& P = m->plan;
+  if (P.dtype != AE_F32 || P.h0 != 1 || P.w0 != 1 || P.hl != 1 || P.wl != 1 || P.cl != P.c0)
+    return fail(AE_EINVAL, "model_monte_carlo: needs a binary32 model that maps k message symbols (in:kx1x1) to k soft bits");
+  const uint64_t B = (uint64_t)P.batch;
+  const uint64_t full = total_samples / B, rest = total_samples % B;
+  if (rest != 0) {
+    if (!m_tail) return fail(AE_EINVAL, "model_monte_carlo: %llu samples leave a last launch of %llu: pass a model of that batch as m_tail",
+                             (unsigned long long)total_samples, (unsigned long long)rest);
+    const Plan& T = m_tail->plan;
+    if ((uint64_t)T.batch != rest || T.dtype != P.dtype || T.c0 != P.c0 || T.cl != P.cl || T.h0 != 1 || T.w0 != 1 ||
+        T.hl != 1 || T.wl != 1 || T.n_params != P.n_params)
+      return fail(AE_EINVAL, "model_monte_carlo: m_tail must be the same network with batch %llu", (unsigned long long)rest);
+  }
+  if (first_sample + total_samples < first_sample) return fail(AE_EINVAL, "model_monte_carlo: sample range wraps around 2^64");
+  const int k = P.c0;
+  for (uint64_t l = 0; l < full + (rest ? 1 : 0); ++l) {
+    ae_model* mm = l < full ? m : m_tail;
+    const int64_t nb = l < full ? (int64_t)B : (int64_t)rest;
+    const uint64_t first = first_sample + l * B;
+    AE_TRY(model_gen_bits(seed, first, nb, k, x_buf, stream));
+    AE_TRY(model_set_sample_offset(mm, first));
+    AE_TRY(model_forward(mm, params, x_buf, snr_db, seed, y_buf, stream));
+    AE_TRY(model_count_errors(y_buf, x_buf, nb, k, bit_err, blk_err, stream));
+  }
+  return AE_OK;
 }
 
 int model_num_steps(const ae_model* m, int* n_steps) {

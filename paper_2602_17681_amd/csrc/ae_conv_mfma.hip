@@ -145,7 +145,12 @@ __device__ __forceinline__ void igemm_store_interior(const floatx16 (&acc)[MI][N
       for (int e = 0; e < 16; ++e) {
         const int lr = (e >> 2) * 8 + row_lane + (e & 3);
         float v = acc[i][j][e] + bias[j];
-        if (STATS) { v = round_to_storage<T>(v); s1[j] += v; s2[j] = fmaf(v, v, s2[j]); }
+        if (STATS) {   // statistics of the stored value, taken about the channel's bias (see k_bn_finalize)
+          v = round_to_storage<T>(v);
+          const float d = v - bias[j];
+          s1[j] += d;
+          s2[j] = fmaf(d, d, s2[j]);
+        }
         if (RELU) v = fmaxf(v, 0.0f);          // rounding is monotonic and keeps 0: same as ReLU of the rounded value
         Store<T>::st(&stage[lr * SW + j * 32 + col_lane], v);
       }
@@ -248,7 +253,7 @@ __device__ __forceinline__ void igemm_epilogue(floatx16 (&acc)[BM / WGM / 32][BN
           const int lr = (e >> 2) * 8 + row_lane + (e & 3);
           const int64_t m = m0 + wm * WM + i * 32 + lr;
           const float v = round_to_storage<T>(acc[i][j][e] + bias);   // the stored conv result
-          if (p.partial && m < p.M && col_ok) { s1[j] += v; s2[j] = fmaf(v, v, s2[j]); }
+          if (p.partial && m < p.M && col_ok) { const float d = v - bias; s1[j] += d; s2[j] = fmaf(d, d, s2[j]); }
           const float a = apply_act(v, p.act);
           if (wide_store) {
             Store<T>::st(&stage[lr * SW + j * 32 + col_lane], a);

@@ -103,8 +103,9 @@ __global__ __launch_bounds__(NT) void k_thin_in_conv(const T* __restrict__ thin,
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       const float v = round_to_storage<T>(acc[c]);
-      s1[c] += v;
-      s2[c] = fmaf(v, v, s2[c]);
+      const float d = v - bs[c];                 // statistics about the channel's bias (see k_bn_finalize)
+      s1[c] += d;
+      s2[c] = fmaf(d, d, s2[c]);
       o[c] = apply_act(v, act);
     }
     T* dst = out + m * CW + 4 * g;

@@ -154,13 +154,18 @@ __device__ __forceinline__ void thin_epilogue(const t_floatx16 (&acc)[2][NJ], co
             if (want_stats) {
               int th, tw;
               thin_row_pixel<false>(wave * 64 + i * 32 + lr, TW, tw_shift, th, tw);
-              if (j * 32 + col_lane < CW && h0 + th < H && w0 + tw < W) { s1[j] += v; s2[j] = fmaf(v, v, s2[j]); }
+              if (j * 32 + col_lane < CW && h0 + th < H && w0 + tw < W) {
+                const float d = v - bs[j];       // statistics about the channel's bias (see k_bn_finalize)
+                s1[j] += d;
+                s2[j] = fmaf(d, d, s2[j]);
+              }
             }
             v = apply_act(v, act);
           } else if (MODE == 1) {
             v = bf16_to_f32(f32_to_bf16(v));
-            s1[j] += v;
-            s2[j] = fmaf(v, v, s2[j]);
+            const float d = v - bs[j];
+            s1[j] += d;
+            s2[j] = fmaf(d, d, s2[j]);
           } else if (MODE == 2) {
             v = fmaxf(v, 0.0f);                  // rounding is monotonic and keeps 0
           }

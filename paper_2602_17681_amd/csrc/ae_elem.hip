@@ -179,9 +179,12 @@ __global__ void k_col_stats(const T* __restrict__ x, int64_t rows, int rpb, int 
 
 // one block per channel: reduce the partials in double and derive the batch-norm vectors
 //   bn_vec = [scale | shift | mean | invstd | c1 | c2], scale = gamma*invstd, shift = beta - mean*scale
+// The partials are sums of (x - k) and (x - k)^2 with k = about[c] (0 when about is null): the variance
+// E[(x-k)^2] - (E[x-k])^2 does not depend on k, and with k the layer's bias the binary32 partial sums of a
+// channel whose mean is far from zero because of its bias no longer cancel against each other.
 __global__ void k_bn_finalize(const float* __restrict__ partial, int nblocks, double inv_rows, int C,
                               const float* __restrict__ gamma_beta, const float* __restrict__ stored_mean_var,
-                              float* __restrict__ bn_vec) {
+                              const float* __restrict__ about, float* __restrict__ bn_vec) {
   __shared__ double sm[NT / 64 + 1];
   const int c = blockIdx.x;
   double mean, var;
@@ -197,9 +200,10 @@ __global__ void k_bn_finalize(const float* __restrict__ partial, int nblocks, do
     }
     s1 = block_sum<NT>(s1, sm);
     s2 = block_sum<NT>(s2, sm);
-    mean = s1 * inv_rows;
-    var = s2 * inv_rows - mean * mean;
+    const double dm = s1 * inv_rows;
+    var = s2 * inv_rows - dm * dm;
     if (var < 0.0) var = 0.0;
+    mean = dm + (about ? (double)about[c] : 0.0);
   }
   if (threadIdx.x == 0) {
     double invstd = 1.0 / sqrt(var + 1e-5);
@@ -774,9 +778,9 @@ int launch_col_stats(const void* x, int64_t rows, int c, int dtype, float* parti
 }
 
 int launch_bn_finalize(const float* partial, int nblocks, int64_t rows, int c, const float* gamma_beta,
-                       const float* stored_mean_var, float* bn_vec, hipStream_t s) {
+                       const float* stored_mean_var, const float* about, float* bn_vec, hipStream_t s) {
   hipLaunchKernelGGL(k_bn_finalize, dim3(c), dim3(NT), 0, s, partial, nblocks, 1.0 / (double)rows, c, gamma_beta,
-                     stored_mean_var, bn_vec);
+                     stored_mean_var, about, bn_vec);
   return launch_status("bn_finalize");
 }
 

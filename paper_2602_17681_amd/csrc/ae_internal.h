@@ -221,8 +221,9 @@ int launch_plane_sums(const void* x, int64_t n, int c, int64_t hw, int dtype, fl
 
 // per-channel reductions and the second pass after a conv
 int launch_col_stats(const void* x, int64_t rows, int c, int dtype, float* partial, hipStream_t s);
+// about: the per-channel constant the partial sums were taken about (the conv epilogues use the bias), or null
 int launch_bn_finalize(const float* partial, int nblocks, int64_t rows, int c, const float* gamma_beta,
-                       const float* stored_mean_var, float* bn_vec, hipStream_t s);
+                       const float* stored_mean_var, const float* about, float* bn_vec, hipStream_t s);
 int launch_post_forward(const void* raw, const float* bn_vec, void* out, int64_t n, int h, int w, int c, int act,
                         int pool, int dtype, hipStream_t s);
 int launch_post_bwd_reduce(const void* raw, const void* dout, const void* out_act, const float* bn_vec, int64_t n, int h,

@@ -124,8 +124,9 @@ __device__ __forceinline__ float sample_sum(float v, float* sm) {
   return block_sum<NT>(v, sm);
 }
 
+// (z and y may be the same buffer: no __restrict__; every lane reads the elements it writes before it writes them)
 template <typename T, bool FLAT, int TPS>
-__global__ void k_pnorm_awgn(const T* __restrict__ z, T* __restrict__ y, int64_t batch, int C, int HW, int do_pnorm,
+__global__ void k_pnorm_awgn(const T* z, T* y, int64_t batch, int C, int HW, int do_pnorm,
                              int do_awgn, float sigma, uint64_t seed, uint64_t first_sample) {
   __shared__ float sm[NT / 64 + 1];
   const int lane = threadIdx.x % TPS;
@@ -179,6 +180,38 @@ __global__ void k_pnorm_awgn(const T* __restrict__ z, T* __restrict__ y, int64_t
       }
     }
   }
+}
+
+// Short flat latents (n = 4 L elements, L a power of two up to 32): L neighbouring lanes own one sample, one
+// quad each, so a wavefront holds 64 / L samples and every lane of it loads, generates and stores; the sum
+// of squares is reduced inside each group of L lanes with xor-shuffles (the same order for every sample,
+// wherever it sits in the batch).  z and y may be the same buffer.
+template <typename T, int L>
+__global__ __launch_bounds__(NT) void k_pnorm_awgn_short(const T* z, T* y, int64_t batch, int do_pnorm, int do_awgn,
+                                                         float sigma, uint64_t seed, uint64_t first_sample) {
+  const int lane = threadIdx.x % L;
+  const int64_t b = (int64_t)blockIdx.x * (NT / L) + (threadIdx.x / L);
+  const bool valid = b < batch;                  // every lane stays for the shuffles
+  float v[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  if (valid) ld4<T>(z + b * (4 * L) + 4 * lane, v);
+  float scale = 1.0f;
+  if (do_pnorm) {
+    float ss = 0.0f;
+    ss = fmaf(v[0], v[0], ss); ss = fmaf(v[1], v[1], ss); ss = fmaf(v[2], v[2], ss); ss = fmaf(v[3], v[3], ss);
+#pragma unroll
+    for (int off = L / 2; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
+    const float ms = ss / (float)(4 * L);
+    scale = ms > 0.0f ? 1.0f / sqrtf(ms) : 0.0f;
+  }
+  float g[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  if (do_awgn) {
+    normal_quad(seed, first_sample + (uint64_t)b, (uint32_t)lane, g);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) g[j] = __fmul_rn(sigma, g[j]);
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) v[j] = __fadd_rn(__fmul_rn(v[j], scale), g[j]);
+  if (valid) st4<T>(y + b * (4 * L) + 4 * lane, v);
 }
 
 // x = z/r: dz = g/r - z * sum(g z) / (n r^3); elementwise in storage order
@@ -276,6 +309,24 @@ int launch_pnorm_awgn(const void* z, void* y, int64_t batch, int c, int hw, int 
   int C = c, HW = hw;
   if (C == 1) { C = HW; HW = 1; }
   const bool flat = HW == 1 && (C % 4 == 0);
+  if (flat && C <= 128 && (C & (C - 1)) == 0) {
+    // short latents: several samples per wavefront
+    const int L = C / 4;
+    const int64_t blocks = (batch + NT / L - 1) / (NT / L);
+    if (blocks > 0x7FFFFFFF) return fail(AE_EINVAL, "pnorm_awgn: batch too large");
+#define LAUNCH_S(T, LV)                                                                                              \
+  hipLaunchKernelGGL((k_pnorm_awgn_short<T, LV>), dim3((unsigned)blocks), dim3(NT), 0, s, (const T*)z, (T*)y, batch, \
+                     do_pnorm, do_awgn, sigma, seed, first_sample)
+#define LAUNCH_SL(T)                                                                                 \
+  switch (L) {                                                                                       \
+    case 1: LAUNCH_S(T, 1); break;   case 2: LAUNCH_S(T, 2); break;   case 4: LAUNCH_S(T, 4); break;  \
+    case 8: LAUNCH_S(T, 8); break;   case 16: LAUNCH_S(T, 16); break; default: LAUNCH_S(T, 32); break; \
+  }
+    if (dtype == AE_BF16) { LAUNCH_SL(bf16_t) } else { LAUNCH_SL(float) }
+#undef LAUNCH_SL
+#undef LAUNCH_S
+    return launch_status("pnorm_awgn_short");
+  }
   const bool wide = block_per_sample(batch, (int64_t)C * HW);
   const int64_t blocks = wide ? batch : (batch + NT / 64 - 1) / (NT / 64);
   if (blocks > 0x7FFFFFFF) return fail(AE_EINVAL, "pnorm_awgn: batch too large");

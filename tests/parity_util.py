@@ -9,11 +9,16 @@ import oracle.ae_oracle as orc
 import workloads as wl
 
 TOL = {"f32": 1e-4, "bf16": 2e-2}
-# The stated tolerances are applied to the relative L2 norm of each tensor.  The largest
-# single deviation, relative to the largest reference magnitude, gets the same bar in fp32;
-# in bf16 it is the tail of ~1e5..1e7 independent rounding errors (4.5-5.5 standard
-# deviations), so its bar is three times the L2 bar.
-TOL_MAX = {"f32": 1e-4, "bf16": 6e-2}
+# The stated tolerances are applied to the relative L2 norm of each tensor.  The largest single deviation, relative to
+# the largest reference magnitude, gets the same bar in fp32.  In bf16 it is the tail of 1e5..1e8 independent
+# rounding errors (4.5-5.5 standard deviations); measured over every case of the suite: at most 2.4e-2 against the
+# oracle that emulates the storage format (all tensors, all sizes), 2.9e-2 for internal activations against the plain
+# oracle, 5.5e-2 for the output y of the deepest network at full size against the plain oracle (the sigmoid output
+# after twelve stored layers).  Hence: 3e-2 against the storage oracle and for gradients, 4e-2 for internal activations
+# and 6e-2 for y against the plain oracle.
+TOL_MAX = {"f32": 1e-4, "bf16": 3e-2}
+TOL_MAX_ACT_PLAIN = {"f32": 1e-4, "bf16": 4e-2}
+TOL_MAX_Y_PLAIN = {"f32": 1e-4, "bf16": 6e-2}
 # Internal activations of a bf16 model against the PLAIN (real-number) oracle: the output y is
 # held to 2e-2, but the error against real-number arithmetic grows with depth (every stored
 # tensor adds a rounding of relative size 2^-9, and zero-mean weights cancel the mean of the
@@ -23,29 +28,25 @@ TOL_MAX = {"f32": 1e-4, "bf16": 6e-2}
 # the plain oracle for y, 3e-2 against the plain oracle for internal activations.
 TOL_ACT_PLAIN = {"f32": 1e-4, "bf16": 3e-2}
 
-# Gradients of LARGE fp32 networks.  A ReLU mask bit or max-pool winner is decided by the sign /
-# order of values that two correct fp32 implementations compute only to ~1e-6 relative; among
-# 1e7 pre-activations a few tens lie that close to the decision boundary, and each flipped
-# decision moves one full-magnitude term of the gradient: relative L2 error ~ sqrt(flipped
-# fraction) ~ 1e-3..5e-3, whatever the kernel does (the small fp32 tests, with 1e3..1e5
-# elements per layer, contain no such element and hold 1e-4).  Full-size fp32 gradients are
-# therefore held to 1e-2 (single largest deviation: 5e-2 of the largest entry, one flipped
-# term) and cosine 0.9999, and the decision-free (linear) layers to 1e-4 at full size on their own.
-LARGE_F32_GRAD = (1e-2, 0.9999)
-
-# Gradient bar for DEEP bf16 networks (relative L2 bound, minimum cosine per tensor).
-# Every ReLU mask bit and max-pool winner is a discrete decision taken on a stored bf16
-# activation.  Two correct implementations of the format (fp32 vs fp64 accumulation order)
-# differ by 1 bf16 ulp (2^-8 relative) on a small fraction of stored values; each such
-# difference perturbs ~9*C_out outputs of the next layer by ~2^-8/sqrt(K), enough to flip
-# the rounding of a few per cent of them, so the fraction of differing values grows with
-# depth until activations agree only to ~5e-3 (still inside the 2e-2 activation bar).  A
-# fraction f of flipped masks / winners changes a gradient tensor by ~sqrt(f) in relative
-# L2 (each flip moves one full-magnitude term), i.e. 5-15 % for f = 0.3-2 %, whatever the
-# kernel does.  Hence: per-layer gradients are held to 2e-2 on single-layer models (same
-# decisions on both sides), and whole deep networks to this derived bar plus direction.
-# The largest single entry of a tensor can be off by about twice the L2 figure.
-DEEP_BF16_GRAD = (0.25, 0.97)
+# Gradients of networks whose ReLU masks / max-pool winners differ between the two sides (deep bf16 networks: two
+# correct implementations of the format differ by one bf16 ulp on a small fraction of stored values, and after a few
+# layers 1e-3..1e-2 of the decisions differ; full-size fp32 networks: a few tens of 1e7 pre-activations lie within
+# fp32 rounding of a decision).  The gradient is discontinuous in those decisions, so such cases are compared twice
+# (run_case(flips=True)):
+#  (1) against the oracle's own chain, with a bar that follows from COUNTING the disagreements
+#      (decisions_of_both_sides: the device's saved tensors against the oracle's; nothing is fed from one side to
+#      the other): every gradient tensor of a layer in step s is held to
+#          relative L2 error  <=  base tolerance  +  FLIP_C * sqrt( sum over steps t >= s of flipped fraction f_t ):
+#      a flipped decision in step t >= s replaces one term of the gradient signal that reaches layer s by another of
+#      typical size (relative change sqrt(f_t) in L2, independent between steps); FLIP_C covers the spread of the
+#      flipped terms' magnitudes around the typical one (measured (error - base) / sqrt(sum f): 1.0 .. 1.9 on the bf16
+#      networks with 1e-3 .. 1e-2 of the decisions flipped, 3.2 on full-size cfg2 in fp32 where ~20 flipped decisions
+#      among 1.7e7 carry the whole error).  No flips at or behind a layer => the plain 1e-4 / 2e-2 bar;
+#  (2) against the oracle's backward pass run under the DEVICE's decisions (only the pass bits and winner indices
+#      are stated to it, oracle/ae_oracle.cpp "given decisions"; every value it uses is its own), where every gradient
+#      tensor must meet the plain 1e-4 / 2e-2 bar: this is the comparison that would catch a kernel that loses a few
+#      per cent of a gradient (measured: <= 1.9e-2 on every bf16 case incl. cfg3 and cfg5 at full size, 4e-6 on cfg2).
+FLIP_C = 4.0
 
 
 def rel_errors(a, o):
@@ -64,15 +65,6 @@ def rel_errors(a, o):
 
 STRICT = os.environ.get("AE_PARITY_NONSTRICT", "") == ""   # unset (debugging only) to collect errors instead of asserting
 REPORT = os.environ.get("AE_PARITY_REPORT", "")              # a file that receives one JSON line per case (measurements)
-
-# Gradients of networks whose ReLU masks / max-pool winners differ between the two sides.  The decisions are
-# COUNTED (count_flips below: the device's saved tensors against the oracle's, nothing is fed from one side to the
-# other) and every gradient tensor of a layer in step s is held to
-#     relative L2 error  <=  base tolerance  +  FLIP_C * sqrt( sum over steps t >= s of flipped fraction f_t ):
-# a flipped decision in step t >= s replaces one term of the gradient signal that reaches layer s by another of
-# typical size (relative change sqrt(f_t) in L2, independent between steps); FLIP_C = 2 covers the spread of the
-# flipped terms' magnitudes around the typical one.  No flips at or behind a layer => the plain 1e-4 / 2e-2 bar.
-FLIP_C = 2.0
 
 
 def assert_close(a, o, tol, what, tol_max=None):
@@ -94,12 +86,13 @@ def _winners(a):
     return a.reshape(b, c, h // 2, 2, w // 2, 2).transpose(0, 1, 2, 4, 3, 5).reshape(b, c, h // 2, w // 2, 4).argmax(axis=-1)
 
 
-def count_flips(m, net, params, batch):
-    """Fraction, per step of the device's plan, of the discrete decisions of the backward pass (ReLU mask bits,
-    max-pool winners) on which the device's saved tensors and the oracle's disagree.  Test-side bookkeeping only:
-    neither side sees the other's values."""
+def decisions_of_both_sides(m, net, params, batch):
+    """Per step of the device's plan that takes discrete decisions in its backward pass (ReLU pass bits, max-pool
+    winners): the fraction of them on which the device's saved tensors and the oracle's disagree, and the device's
+    decisions as arrays keyed by the oracle's op index (uint8, shape of that op's output: relu pass bits, pool2
+    winner indices).  Test-side bookkeeping computed from the two sides' saved tensors."""
     import torch
-    flips, prev = {}, -1
+    flips, dec, prev = {}, {}, -1
     for s in range(m.model_num_steps()):
         tok, chw = m.model_step_info(s)
         first, prev = prev + 1, tok
@@ -124,15 +117,22 @@ def count_flips(m, net, params, batch):
             w_d = _winners(raw_d)
             del raw_d
             w_o = _winners(net.activation(ipool - 1).reshape((batch,) + cshape))
+            dec[ipool] = w_d.astype(np.uint8)
             if "relu" in kinds:
                 a_d, a_o = out_d > 0, out_o > 0
                 flip = (a_d != a_o) | (a_d & a_o & (w_d != w_o))
+                # pass bits at convolution resolution: only a window's winner can receive a gradient at all
+                b, c, ho, wo = w_d.shape
+                onehot = (np.arange(4, dtype=np.uint8)[None, None, None, None, :] == w_d[..., None].astype(np.uint8)) & a_d[..., None]
+                dec[first + kinds.index("relu")] = np.ascontiguousarray(
+                    onehot.reshape(b, c, ho, wo, 2, 2).transpose(0, 1, 2, 4, 3, 5).reshape(b, c, 2 * ho, 2 * wo).astype(np.uint8))
             else:
                 flip = w_d != w_o
         else:
             flip = (out_d > 0) != (out_o > 0)
+            dec[first + kinds.index("relu")] = (out_d > 0).astype(np.uint8)
         flips[s] = float(flip.mean())
-    return flips
+    return flips, dec
 
 
 def run_case(spec, batch, dtype="f32", seed=0, snr_db=10.0, first_sample=0, bn_mode=0, backward=True,
@@ -176,7 +176,8 @@ def run_case(spec, batch, dtype="f32", seed=0, snr_db=10.0, first_sample=0, bn_m
     worst = {}
     y_gpu = y_d.float().cpu().numpy()
     for (rname, _), y_ref in zip(refs, y_refs):
-        worst["y/" + rname] = assert_close(y_gpu, y_ref, tol, "y vs %s oracle" % rname, tol_max=tolm)
+        worst["y/" + rname] = assert_close(y_gpu, y_ref, tol, "y vs %s oracle" % rname,
+                                           tol_max=TOL_MAX_Y_PLAIN[dtype] if rname == "plain" else tolm)
     if check_acts:
         ns = m.model_num_steps()
         for s in range(ns):
@@ -191,10 +192,11 @@ def run_case(spec, batch, dtype="f32", seed=0, snr_db=10.0, first_sample=0, bn_m
                 ref = rnet.activation(tok).reshape((batch,) + chw)
                 atol = TOL_ACT_PLAIN[dtype] if rname == "plain" else tol
                 worst["act%d/%s" % (s, rname)] = assert_close(
-                    got, ref, atol, "activation of step %d (token %d) vs %s oracle" % (s, tok, rname), tol_max=tolm)
-    step_of_op, cum = {}, {}
+                    got, ref, atol, "activation of step %d (token %d) vs %s oracle" % (s, tok, rname),
+                    tol_max=TOL_MAX_ACT_PLAIN[dtype] if rname == "plain" else tolm)
+    step_of_op, cum, dec = {}, {}, {}
     if backward and flips:
-        fl = count_flips(m, net, params, batch)
+        fl, dec = decisions_of_both_sides(m, net, params, batch)
         worst["flips"] = fl
         prev, tot = -1, 0.0
         ns = m.model_num_steps()
@@ -220,30 +222,44 @@ def run_case(spec, batch, dtype="f32", seed=0, snr_db=10.0, first_sample=0, bn_m
         g = g_d.cpu().numpy()
         assert np.all(np.isfinite(g))
         ent, _, _, _ = wl.param_layout(spec, bn_mode)
-        for e in ent:
-            sz = int(np.prod(e["shape"]))
-            sl = slice(e["offset"], e["offset"] + sz)
-            name = "grad %s.%s@%d" % (e["name"], e["kind"], e["op"])
-            if np.abs(g_ref[sl]).max() == 0.0:
-                assert np.abs(g[sl]).max() == 0.0, name
-                continue
-            if e["kind"] == "b" and _feeds_batch_bn(spec, e["op"], bn_mode):
-                # analytically zero: compare against the scale of the layer's weight gradient instead
-                wsl = [q for q in ent if q["op"] == e["op"] and q["kind"] == "w"][0]
-                scale = np.abs(g_ref[wsl["offset"]:wsl["offset"] + int(np.prod(wsl["shape"]))]).max()
-                if STRICT:
-                    assert np.abs(g[sl]).max() <= max(gtol, 1e-3) * scale * 10, name
-                continue
-            if flips:
-                bound = gtol + FLIP_C * float(np.sqrt(cum[step_of_op[e["op"]]]))
-                worst[name] = assert_close(g[sl], g_ref[sl], bound, name, tol_max=max(tolm, 3 * bound)) + (bound,)
-                continue
-            worst[name] = assert_close(g[sl], g_ref[sl], gtol, name, tol_max=max(2 * gtol, 5e-2) if grad_cos is not None else max(gtol, tolm))
-            if grad_cos is not None and sz >= 16:
-                c = float(np.dot(g[sl], g_ref[sl]) / (np.linalg.norm(g[sl]) * np.linalg.norm(g_ref[sl])))
-                worst[name] = worst[name] + (c,)
-                if STRICT:
-                    assert c >= grad_cos, "%s: cosine %.4f < %.4f" % (name, c, grad_cos)
+
+        def compare(g_ref, prefix, bound_of, max_of):
+            for e in ent:
+                sz = int(np.prod(e["shape"]))
+                sl = slice(e["offset"], e["offset"] + sz)
+                name = "%s %s.%s@%d" % (prefix, e["name"], e["kind"], e["op"])
+                if np.abs(g_ref[sl]).max() == 0.0:
+                    assert np.abs(g[sl]).max() == 0.0, name
+                    continue
+                if e["kind"] == "b" and _feeds_batch_bn(spec, e["op"], bn_mode):
+                    # analytically zero: compare against the scale of the layer's weight gradient instead
+                    wsl = [q for q in ent if q["op"] == e["op"] and q["kind"] == "w"][0]
+                    scale = np.abs(g_ref[wsl["offset"]:wsl["offset"] + int(np.prod(wsl["shape"]))]).max()
+                    if STRICT:
+                        assert np.abs(g[sl]).max() <= max(gtol, 1e-3) * scale * 10, name
+                    continue
+                bound = bound_of(e)
+                worst[name] = assert_close(g[sl], g_ref[sl], bound, name, tol_max=max_of(bound)) + (bound,)
+                if grad_cos is not None and sz >= 16:
+                    c = float(np.dot(g[sl], g_ref[sl]) / (np.linalg.norm(g[sl]) * np.linalg.norm(g_ref[sl])))
+                    worst[name] = worst[name] + (c,)
+                    if STRICT:
+                        assert c >= grad_cos, "%s: cosine %.4f < %.4f" % (name, c, grad_cos)
+
+        if flips:
+            # (1) the oracle's own chain, untouched: bar from the counted disagreements (one flipped term can move a
+            #     single entry by its full size, so the largest deviation gets ten times the L2 bound)
+            compare(g_ref, "grad", lambda e: gtol + FLIP_C * float(np.sqrt(cum[step_of_op[e["op"]]])), lambda b: max(tolm, 10 * b))
+            # (2) the arithmetic of the backward pass under the same decisions: the oracle is TOLD the device's pass
+            #     bits and winners (decisions only; every value it uses is its own) and must then agree at the plain bar
+            for i, d in dec.items():
+                net.set_decisions(i, d)
+            g_same, _ = net.backward(params, cot.astype(np.float64))
+            for i in dec:
+                net.set_decisions(i, None)
+            compare(g_same, "grad/same-decisions", lambda e: gtol, lambda b: max(gtol, tolm))
+        else:
+            compare(g_ref, "grad", lambda e: gtol, lambda b: max(gtol, tolm))
     m.close()
     if REPORT:
         with open(REPORT, "a") as f:

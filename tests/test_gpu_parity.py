@@ -6,7 +6,7 @@ import pytest
 
 import oracle.ae_oracle as orc
 import workloads as wl
-from parity_util import DEEP_BF16_GRAD, LARGE_F32_GRAD, TOL, assert_close, rel_errors, run_case, to_dev
+from parity_util import TOL, assert_close, rel_errors, run_case, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -58,7 +58,8 @@ def test_gen_bits_bit_exact_and_count_errors(ae):
 
 # ------------------------------------------------------------------ channel kernel alone
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("batch,n", [(1000, 128), (64, 64), (7, 4096), (5, 1024), (3, 36)])
+@pytest.mark.parametrize("batch,n", [(1000, 128), (64, 64), (7, 4096), (5, 1024), (3, 36), (513, 8), (33, 4), (70001, 32), (9, 256),
+                                     (11, 192)])
 def test_pnorm_awgn_standalone(ae, dtype, batch, n):
     import torch
     rng = np.random.default_rng(n)
@@ -69,6 +70,9 @@ def test_pnorm_awgn_standalone(ae, dtype, batch, n):
     zd = to_dev(z, dtype, torch)
     yd = torch.empty_like(zd)
     ae.model_pnorm_awgn(zd, yd, batch, n, 5.0, 42, 1000)
+    zi = zd.clone()
+    ae.model_pnorm_awgn(zi, zi, batch, n, 5.0, 42, 1000)        # in place: the header allows y to be z
+    assert torch.equal(zi, yd)
     net = orc.Net("in:%dx1x1,pnorm,awgn" % n, batch)
     ref = net.forward(np.zeros(0, np.float32), z.reshape(batch, n, 1, 1), snr_db=5.0, seed=42, first_sample=1000)
     got = yd.float().cpu().numpy()
@@ -111,6 +115,20 @@ def test_small_networks_forward_backward(ae, case, dtype):
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_stored_statistics_batch_norm(ae, dtype):
     run_case("in:3x8x8,conv3:8,bn,relu,pool2,conv1:4,sigmoid", 4, dtype=dtype, seed=5, bn_mode=1)
+
+
+def test_batch_norm_statistics_of_channels_far_from_zero(ae):
+    """Conv biases of 30-50 standard deviations of the conv result put every channel mean far from zero, where a
+    variance formed as E[x^2] - mean^2 from binary32 partial sums would lose the 1e-4 bar; the kernels take their
+    partial sums about the bias.  First layer through the thin kernel, second through the implicit-GEMM epilogue."""
+    spec = "in:3x16x16,conv3:64,bn,relu,pool2,conv3:64,bn,relu,pool2,conv1:4,sigmoid"
+    params = wl.make_params(spec, 21, perturb=True)
+    ent, _, _, _ = wl.param_layout(spec)
+    rng = np.random.default_rng(21)
+    for e in ent:
+        if e["kind"] == "b" and e["name"].startswith("conv3"):
+            params[e["offset"]:e["offset"] + e["shape"][0]] = (40.0 + 10.0 * rng.standard_normal(e["shape"][0])).astype(np.float32)
+    run_case(spec, 8, dtype="f32", seed=21, snr_db=10.0, params=params)
 
 
 def test_sample_offset_partition_invariance(ae):
@@ -175,14 +193,17 @@ def test_cfg2_reduced_resolution(ae, snr_db):
 
 def test_cfg3_reduced_resolution_bf16(ae):
     spec = wl.scaled_spec("cfg3", 16)
-    run_case(spec, 6, dtype="bf16", seed=2, snr_db=5.0, grad_tol=DEEP_BF16_GRAD[0], grad_cos=DEEP_BF16_GRAD[1])
+    run_case(spec, 6, dtype="bf16", seed=2, snr_db=5.0, flips=True)
 
 
-def test_cfg4_launch_and_error_counts(ae):
+@pytest.mark.parametrize("first,B,snr_db", [
+    (0, 65536, -2.0),                    # launch 0
+    (65536 * 5, 65536, 2.0), (65536 * 700, 65536, 0.0),      # two launches from the middle of the run
+    (65536 * 1525, 57600, 4.0)])         # the last, shorter launch of the 1e8-sample run
+def test_cfg4_launch_and_error_counts(ae, first, B, snr_db):
     import torch
     cfg = wl.CONFIGS["cfg4"]
-    B, K = cfg["batch"], 64          # one full launch of 65 536 samples
-    first = 65536 * 5
+    K = 64
     spec = cfg["spec"]
     params = wl.make_params(spec, cfg["seed"])
     m = ae.Model(spec, B)
@@ -193,12 +214,12 @@ def test_cfg4_launch_and_error_counts(ae):
     ke = torch.zeros(1, dtype=torch.int64, device="cuda")
     ae.model_gen_bits(cfg["seed"], first, B, K, x)
     m.model_set_sample_offset(first)
-    m.model_forward(pd, x, 2.0, cfg["seed"], y)
+    m.model_forward(pd, x, snr_db, cfg["seed"], y)
     ae.model_count_errors(y, x, B, K, be, ke)
     xr = orc.gen_bits(cfg["seed"], first, B, K)
     assert np.array_equal(x.cpu().numpy().reshape(B, K), xr)
     net = orc.Net(spec, B)
-    yr = net.forward(params, xr.reshape(B, K, 1, 1), snr_db=2.0, seed=cfg["seed"], first_sample=first)
+    yr = net.forward(params, xr.reshape(B, K, 1, 1), snr_db=snr_db, seed=cfg["seed"], first_sample=first)
     assert_close(y.cpu().numpy(), yr, 1e-4, "cfg4 y")
     # decisions agree except where the reference output sits within rounding of the threshold
     yg = y.cpu().numpy().reshape(B, K)
@@ -210,11 +231,62 @@ def test_cfg4_launch_and_error_counts(ae):
     assert (int(be.item()), int(ke.item())) == (rb, rk)
     ob, _ = orc.count_errors(yo, xr)
     assert abs(rb - ob) <= int(near.sum())
+    m.close()
+
+
+def test_monte_carlo_run_in_launches_with_a_shorter_last_one(ae):
+    """model_monte_carlo over a sample range that is not a multiple of the launch size (three launches of 4 096 and one
+    of 1 000 on a second handle, starting across the 2^32 sample boundary): the two counters, read once, against the
+    oracle run over the whole range as one batch, and against the same range done call by call."""
+    import torch
+    cfg = wl.CONFIGS["cfg4"]
+    spec, seed, K = cfg["spec"], cfg["seed"], 64
+    B, rest = 4096, 1000
+    total, first = 3 * B + rest, (1 << 32) - 5000
+    params = wl.make_params(spec, seed)
+    pd = torch.from_numpy(params).cuda()
+    m, tail = ae.Model(spec, B), ae.Model(spec, rest)
+    for h in (m, tail):
+        h.model_set_params_static(True)
+    x, y = torch.empty((B, K), device="cuda"), torch.empty((B, K), device="cuda")
+    be = torch.zeros(1, dtype=torch.int64, device="cuda")
+    ke = torch.zeros(1, dtype=torch.int64, device="cuda")
+    ae.model_monte_carlo(m, tail, pd, 1.0, seed, first, total, x, y, be, ke)
+    got = (int(be.item()), int(ke.item()))
+    # the same range call by call
+    be2, ke2 = torch.zeros_like(be), torch.zeros_like(ke)
+    ys = []
+    for l in range(4):
+        h, nb = (m, B) if l < 3 else (tail, rest)
+        f = first + l * B
+        ae.model_gen_bits(seed, f, nb, K, x[:nb])
+        h.model_set_sample_offset(f)
+        h.model_forward(pd, x[:nb], 1.0, seed, y[:nb])
+        ae.model_count_errors(y[:nb], x[:nb], nb, K, be2, ke2)
+        ys.append(y[:nb].cpu().numpy().copy())
+    assert got == (int(be2.item()), int(ke2.item()))
+    # the oracle over the whole range at once (no batch coupling in this network)
+    xr = orc.gen_bits(seed, first, total, K)
+    yo = orc.Net(spec, total).forward(params, xr.reshape(total, K, 1, 1), snr_db=1.0, seed=seed, first_sample=first).reshape(total, K)
+    yg = np.concatenate(ys)
+    assert_close(yg, yo, 1e-4, "monte-carlo y")
+    near = np.abs(yo - 0.5) < 1e-4
+    assert got == orc.count_errors(yg.astype(np.float64), xr)
+    ob, ok = orc.count_errors(yo, xr)
+    assert abs(got[0] - ob) <= int(near.sum()) and abs(got[1] - ok) <= int(near.any(axis=1).sum())
+    # argument checks: a remainder without a second handle, a second handle of the wrong batch
+    with pytest.raises(ae.AeError):
+        ae.model_monte_carlo(m, None, pd, 1.0, seed, 0, total, x, y, be, ke)
+    with pytest.raises(ae.AeError):
+        ae.model_monte_carlo(m, m, pd, 1.0, seed, 0, total, x, y, be, ke)
+    ae.model_monte_carlo(m, None, pd, 1.0, seed, 0, 2 * B, x, y, be, ke)      # a multiple needs none
+    m.close()
+    tail.close()
 
 
 def test_cfg5_reduced_resolution_bf16(ae):
     spec = wl.scaled_spec("cfg5", 64)     # 2x2 pixels after the fifth pool: batch-norm still sees 16 values per channel
-    run_case(spec, 4, dtype="bf16", seed=4, snr_db=10.0, grad_tol=DEEP_BF16_GRAD[0], grad_cos=DEEP_BF16_GRAD[1])
+    run_case(spec, 4, dtype="bf16", seed=4, snr_db=10.0, flips=True)
 
 
 # ------------------------------------------------------------------ single layers in bf16: gradients at 2e-2
@@ -232,7 +304,7 @@ LAYERS_BF16 = [
     # No ReLU behind the upsampled conv: its summed weights are rounded to bf16 once more, which moves the stored
     # bf16 outputs by an ulp here and there (2.5e-3 in relative L2, inside the 2e-2 bar), and a ReLU mask taken on
     # them would then differ from the oracle's in ~0.2 % of the elements: sqrt(0.002) = 4 % in every gradient,
-    # whatever the kernels do (see DEEP_BF16_GRAD); without it the gradients test the two forms themselves.
+    # whatever the kernels do (see FLIP_C in parity_util.py); without it the gradients test the two forms themselves.
     ("in:64x16x16,conv3:64,relu,up2,conv3:64", 32),
 ]
 
@@ -362,8 +434,7 @@ def test_calibration_loop_and_its_argument_checks(ae):
 def test_cfg2_full_size_forward_backward(ae):
     """cfg2 exactly as bench.py runs it (batch 256, 3x32x32, fp32), every activation and gradient."""
     cfg = wl.CONFIGS["cfg2"]
-    run_case(cfg["spec"], cfg["batch"], dtype="f32", seed=cfg["seed"], snr_db=5.0, perturb=False,
-             grad_tol=LARGE_F32_GRAD[0], grad_cos=LARGE_F32_GRAD[1])
+    run_case(cfg["spec"], cfg["batch"], dtype="f32", seed=cfg["seed"], snr_db=5.0, perturb=False, flips=True)
 
 
 FULL_SIZE_LINEAR = [
@@ -385,24 +456,26 @@ def test_full_size_linear_layers(ae, case):
     run_case(spec, batch, dtype=dtype, seed=400 + case, snr_db=10.0)
 
 
-def test_cfg3_full_size_forward(ae):
-    """cfg3 at its full size (batch 128, 3x64x64, bf16): forward against both oracles."""
+def test_cfg3_full_size_forward_backward(ae):
+    """cfg3 at its full size (batch 128, 3x64x64, bf16) as bench.py runs it: y and every saved activation against both
+    oracles, every gradient of the training step (the upstream gradient is the MSE gradient) against the oracle."""
     cfg = wl.CONFIGS["cfg3"]
-    run_case(cfg["spec"], cfg["batch"], dtype="bf16", seed=cfg["seed"], snr_db=5.0, perturb=False, backward=False)
+    run_case(cfg["spec"], cfg["batch"], dtype="bf16", seed=cfg["seed"], snr_db=5.0, perturb=False, flips=True, cot="mse")
 
 
-def test_cfg5_full_size_forward(ae):
-    """cfg5 at its full size (batch 32, 3x256x256, bf16), the launch configuration bench.py times:
-    y and every saved activation against the plain and the bf16-storage oracle."""
+def test_cfg5_full_size_forward_backward(ae):
+    """cfg5 at its full size (batch 32, 3x256x256, bf16), the launch configuration bench.py times: y and every saved
+    activation against the plain and the bf16-storage oracle, and every gradient of the training step (forward,
+    MSE gradient, backward) against the oracle — with the bar that follows from the counted decision flips, and at
+    2e-2 under the same decisions."""
     cfg = wl.CONFIGS["cfg5"]
-    run_case(cfg["spec"], cfg["batch"], dtype="bf16", seed=cfg["seed"], snr_db=10.0, perturb=False, backward=False)
+    run_case(cfg["spec"], cfg["batch"], dtype="bf16", seed=cfg["seed"], snr_db=10.0, perturb=False, flips=True, cot="mse")
 
 
 def test_cfg5_full_resolution_backward_small_batch(ae):
-    """Backward of cfg5 at full 256x256 resolution (batch 2: what the oracle finishes in seconds)."""
+    """Backward of cfg5 at full 256x256 resolution with a generic (random) upstream gradient, batch 2."""
     cfg = wl.CONFIGS["cfg5"]
-    run_case(cfg["spec"], 2, dtype="bf16", seed=cfg["seed"], snr_db=10.0, perturb=False, check_acts=False,
-             grad_tol=DEEP_BF16_GRAD[0], grad_cos=DEEP_BF16_GRAD[1])
+    run_case(cfg["spec"], 2, dtype="bf16", seed=cfg["seed"], snr_db=10.0, perturb=False, check_acts=False, flips=True)
 
 
 def test_cfg5_full_size_backward_properties(ae):

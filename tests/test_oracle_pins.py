@@ -490,3 +490,81 @@ def test_store_bf16_rounding_points_and_values():
     n = orc.Net("in:%dx1x1,relu" % v.size, 1, store_bf16=True)     # relu output is stored
     out = n.forward(np.zeros(0, np.float32), np.abs(v).reshape(1, -1, 1, 1)).ravel()
     np.testing.assert_array_equal(out, wl.round_to_bf16(np.abs(v)).astype(np.float64))
+
+
+def test_store_bf16_rounds_the_gradients_of_stored_tensors():
+    """Backward under the storage emulation, recomputed by hand on a two-layer chain: the gradient handed from a layer
+    to the one before it (the gradient of a stored tensor) is rounded to bfloat16, parameter gradients are not, and
+    they are formed from the rounded gradients."""
+    spec = "in:5x1x1,fc:4,relu,fc:3"
+    B = 6
+    params = wl.make_params(spec, 41, perturb=True, bf16=True)
+    x = wl.make_input(spec, B, 41, bf16=True)
+    ent, _, _, _ = wl.param_layout(spec)
+    w1, b1, w2, b2 = (params[e["offset"]:e["offset"] + int(np.prod(e["shape"]))].reshape(e["shape"]).astype(np.float64) for e in ent)
+    rb = lambda a: wl.round_to_bf16(np.asarray(a, np.float32)).astype(np.float64)
+    emu = orc.Net(spec, B, store_bf16=True)
+    emu.forward(params, x)
+    dy = rb(np.random.default_rng(41).standard_normal((B, 3, 1, 1)))
+    g, dx = emu.backward(params, dy)
+    xx = x.reshape(B, 5).astype(np.float64)
+    h1 = rb(xx @ w1.T + b1)                              # stored fc output
+    a1 = rb(np.maximum(h1, 0.0))                         # stored relu output
+    d2 = dy.reshape(B, 3)
+    da1 = rb(d2 @ w2)                                    # gradient of the stored relu output: rounded
+    assert not np.array_equal(da1, d2 @ w2)
+    dh1 = rb(da1 * (h1 > 0))                             # gradient of the stored fc output (rounding changes nothing here)
+    ref = np.concatenate([(dh1.T @ xx).ravel(), dh1.sum(0), (d2.T @ a1).ravel(), d2.sum(0)])
+    np.testing.assert_allclose(g, ref, rtol=1e-12, atol=1e-15)
+    np.testing.assert_array_equal(dx.reshape(B, 5), rb(dh1 @ w1))
+    plain = orc.Net(spec, B)
+    plain.forward(params, x)
+    assert not np.allclose(plain.backward(params, dy)[0], g, rtol=1e-9, atol=0)   # the plain oracle rounds nothing
+
+
+# ------------------------------------------------------------------ backward with stated decisions
+def test_backward_with_given_decisions_by_hand_and_against_its_own():
+    """The oracle's backward can be told the ReLU pass bits and the max-pool winners instead of taking them from its
+    forward values (used to compare the arithmetic of two backward passes whose forward values differ by rounding).
+    By hand on one 2x2 window; and on a network: its own decisions, stated, reproduce the ordinary gradients exactly,
+    while a changed winner moves the gradient where the definition says."""
+    z = np.zeros(0, np.float32)
+    n = orc.Net("in:1x2x2,relu,pool2", 1)
+    n.forward(z, np.array([[[[1, 2], [3, -1]]]], np.float32))
+    one = np.ones((1, 1, 1, 1))
+    assert np.array_equal(n.backward(z, one)[1].ravel(), [0, 0, 1, 0])            # own decisions: winner (1,0)
+    n.set_decisions(1, np.array([1], np.uint8))                                   # winner := (0,1)
+    assert np.array_equal(n.backward(z, one)[1].ravel(), [0, 1, 0, 0])
+    n.set_decisions(0, np.array([1, 0, 1, 1], np.uint8))                          # and the ReLU blocks that element
+    assert np.array_equal(n.backward(z, one)[1].ravel(), [0, 0, 0, 0])
+    n.set_decisions(0, None)
+    n.set_decisions(1, None)
+    assert np.array_equal(n.backward(z, one)[1].ravel(), [0, 0, 1, 0])
+    with pytest.raises(ValueError):
+        n.set_decisions(1, np.zeros(4, np.uint8))                                 # wrong size
+    with pytest.raises(ValueError):
+        n.set_decisions(5, np.zeros(1, np.uint8))
+    spec = "in:2x6x8,conv3:5,bn,relu,pool2,conv3:4,relu,flatten,fc:6,pnorm,awgn,fc:48,reshape:4x3x4,up2,conv3:2,sigmoid"
+    B = 3
+    net = orc.Net(spec, B)
+    params = wl.make_params(spec, 5, perturb=True)
+    x = wl.make_input(spec, B, 5)
+    y = net.forward(params, x, snr_db=8.0, seed=5)
+    cot = np.random.default_rng(5).standard_normal(y.shape)
+    g0, dx0 = net.backward(params, cot)
+    kinds = [o["kind"] for o in net.ops[1:]]
+    for i, k in enumerate(kinds):
+        if k == "relu":
+            net.set_decisions(i, (net.activation(i - 1) > 0).astype(np.uint8))
+        elif k == "pool2":
+            a = net.activation(i - 1)
+            b, c, h, w = a.shape
+            win = a.reshape(b, c, h // 2, 2, w // 2, 2).transpose(0, 1, 2, 4, 3, 5).reshape(b, c, h // 2, w // 2, 4).argmax(-1)
+            net.set_decisions(i, win.astype(np.uint8))
+    g1, dx1 = net.backward(params, cot)
+    assert np.array_equal(g0, g1) and np.array_equal(dx0, dx1)
+    ipool = kinds.index("pool2")
+    win[0, 0, 0, 0] = (win[0, 0, 0, 0] + 1) % 4
+    net.set_decisions(ipool, win.astype(np.uint8))
+    g2, _ = net.backward(params, cot)
+    assert not np.array_equal(g0, g2)
