@@ -191,6 +191,14 @@ int model_timing_enable(ae_model* m, int on);
  * behaviour while per-kernel timing is enabled, so that each measured duration belongs to
  * one kernel alone).  Results are identical either way. */
 int model_set_overlap(ae_model* m, int on);
+/* Inference mode (on = 1): forward passes keep nothing for a backward pass — model_backward, model_get_activation
+ * and model_get_conv_output then return AE_ESTATE — which lets the executor take paths that never write the
+ * intermediate tensors.  Today that is the three-launch path for small-image networks of the shape
+ *   conv3,bn,relu,pool2, conv3,bn,relu,pool2, flatten, fc, pnorm, awgn, fc, reshape, up2,conv3,relu, up2,conv3,sigmoid
+ * (binary32, batch statistics, images up to 32 x 32, at most 4 channels in and out, hidden channel counts
+ * multiples of 16), where one workgroup keeps a sample's tensors in LDS; every other network runs its usual
+ * kernels.  Results are the same definitions in binary32 (summation order differs).  Default: off. */
+int model_set_inference(ae_model* m, int on);
 /* Every pass converts the binary32 parameter blob into the kernels' operand layouts (the blob may change between
  * calls).  on = 1 is the caller's promise that the CONTENTS of params stay the same from call to call (repeated
  * evaluation, Monte-Carlo launches): the conversion then runs only in the first forward and the first backward
@@ -330,6 +338,15 @@ int model_lu_timing(int enable, double* gemm_ms, int64_t* launches);
  *   workspace model_qr_compose left, same parameters and squarings), the triangular factor is inverted as in
  *   model_lu_inverse; d: a multiple of 128; workspace: model_lu_inverse_workspace(d) bytes. */
 int model_qr_workspace(int64_t d, int squarings, int64_t* bytes);
+/* The number of squarings model_qr_compose needs for the generator g: the smallest J with 2^J >= 2 ||S||_inf,
+ * S = (G - G^T)/2 (the row-sum norm bounds the spectral norm of a skew-symmetric matrix), written to *squarings
+ * (host).  model_qr_compose itself trusts its `squarings` argument: with too few the polynomial is evaluated
+ * outside the range where its truncation error is at rounding level, and the result is an inaccurate (though
+ * still nearly orthogonal) factor without any error being reported — call this when the norm of the generator
+ * is not known to be small.  SYNCHRONOUS, unlike the other calls: it runs three small kernels on `stream`, waits
+ * for them and reads one float back.  workspace: at least model_qr_workspace(d, 0) bytes (contents destroyed).
+ * AE_EINVAL when the generator holds a NaN / infinity or would need more than 16 squarings. */
+int model_qr_squarings(const float* g, int64_t d, void* workspace, int* squarings, void* stream);
 int model_qr_compose(const float* g, const float* rp, const float* log_s, const float* sign_s, int64_t d, int dtype,
                      int squarings, void* a_out, void* workspace, void* stream);
 int model_qr_backward(const void* g_a, const float* rp, const float* log_s, const float* sign_s, int64_t d, int dtype,

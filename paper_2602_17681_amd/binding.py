@@ -22,8 +22,8 @@ SYMBOLS = [
     "model_describe", "model_create", "model_destroy", "model_param_count", "model_io_shape",
     "model_set_sample_offset", "model_forward", "model_backward", "model_loss_mse", "model_noise",
     "model_pnorm_awgn", "model_gen_bits", "model_count_errors", "model_monte_carlo", "model_num_steps", "model_step_info",
-    "model_get_activation", "model_get_conv_output", "model_timing_enable", "model_set_overlap", "model_set_params_static", "model_calibrate_mfma", "model_mx_quantize", "model_mx_quantize_elem", "model_transform_mse_workspace",
-    "model_transform_mse", "model_transform_mse_elem", "model_transform_mse_static", "model_inverse_shift", "model_lu_workspace", "model_lu_compose", "model_lu_backward", "model_vol_penalty", "model_lu_inverse_workspace", "model_lu_inverse", "model_lu_compose_batch", "model_lu_backward_batch", "model_lu_inverse_batch", "model_lu_timing", "model_qr_workspace", "model_qr_compose", "model_qr_backward", "model_qr_inverse", "model_fold_workspace", "model_fold_linear", "model_fold_embedding", "model_timing_slots",
+    "model_get_activation", "model_get_conv_output", "model_timing_enable", "model_set_overlap", "model_set_params_static", "model_set_inference", "model_calibrate_mfma", "model_mx_quantize", "model_mx_quantize_elem", "model_transform_mse_workspace",
+    "model_transform_mse", "model_transform_mse_elem", "model_transform_mse_static", "model_inverse_shift", "model_lu_workspace", "model_lu_compose", "model_lu_backward", "model_vol_penalty", "model_lu_inverse_workspace", "model_lu_inverse", "model_lu_compose_batch", "model_lu_backward_batch", "model_lu_inverse_batch", "model_lu_timing", "model_qr_workspace", "model_qr_squarings", "model_qr_compose", "model_qr_backward", "model_qr_inverse", "model_fold_workspace", "model_fold_linear", "model_fold_embedding", "model_timing_slots",
     "model_timing_read", "model_timing_reset", "model_last_error",
 ]
 
@@ -62,6 +62,7 @@ def _load():
     L.model_timing_enable.argtypes = [vp, C.c_int]
     L.model_set_overlap.argtypes = [vp, C.c_int]
     L.model_set_params_static.argtypes = [vp, C.c_int]
+    L.model_set_inference.argtypes = [vp, C.c_int]
     L.model_calibrate_mfma.argtypes = [C.c_int, C.c_int, C.c_int, vp, C.POINTER(C.c_double), C.POINTER(C.c_double), vp]
     L.model_mx_quantize.argtypes = [vp, vp, C.c_int64, C.c_int64, C.c_int, C.c_int, vp]
     L.model_mx_quantize_elem.argtypes = [vp, vp, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int, vp]
@@ -81,6 +82,7 @@ def _load():
     L.model_lu_backward_batch.argtypes = [vp, vp, vp, vp, vp, vp, C.c_int64, C.c_int64, C.c_int, vp, vp, vp, vp]
     L.model_lu_inverse_batch.argtypes = [vp, vp, vp, vp, vp, C.c_int64, C.c_int64, C.c_int, vp, vp]
     L.model_qr_workspace.argtypes = [C.c_int64, C.c_int, i64p]
+    L.model_qr_squarings.argtypes = [vp, C.c_int64, vp, C.POINTER(C.c_int), vp]
     L.model_qr_compose.argtypes = [vp, vp, vp, vp, C.c_int64, C.c_int, C.c_int, vp, vp, vp]
     L.model_qr_backward.argtypes = [vp, vp, vp, vp, C.c_int64, C.c_int, C.c_int, vp, vp, vp, vp, vp]
     L.model_qr_inverse.argtypes = [vp, vp, vp, C.c_int64, C.c_int, C.c_int, vp, vp, vp, vp]
@@ -189,6 +191,9 @@ class Model:
 
     def model_set_overlap(self, on):
         _check(lib.model_set_overlap(self._h, 1 if on else 0))
+
+    def model_set_inference(self, on):
+        _check(lib.model_set_inference(self._h, 1 if on else 0))
 
     def model_set_params_static(self, on):
         _check(lib.model_set_params_static(self._h, 1 if on else 0))
@@ -386,6 +391,14 @@ def model_qr_workspace(d, squarings=5):
     n = C.c_int64()
     _check(lib.model_qr_workspace(d, squarings, C.byref(n)))
     return n.value
+
+
+def model_qr_squarings(g, d, workspace):
+    """The number of squarings the generator needs (synchronous: reads one float back)."""
+    assert g.numel() == d * d and workspace.numel() * workspace.element_size() >= model_qr_workspace(d, 0)
+    j = C.c_int(-1)
+    _check(lib.model_qr_squarings(_ptr(g, torch.float32), d, _ptr(workspace), C.byref(j), _stream()))
+    return j.value
 
 
 def model_qr_compose(g, rp, log_s, sign_s, d, a_out, workspace, squarings=5):

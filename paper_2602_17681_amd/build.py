@@ -12,8 +12,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libaemodel.so")
-SOURCES = ["ae_plan.cpp", "ae_elem.hip", "ae_noise.hip", "ae_conv_direct.hip", "ae_conv_mfma.hip", "ae_conv_thin.hip", "ae_conv_thin_mfma.hip", "ae_calib.hip", "ae_mx.hip", "ae_affine.hip", "ae_fold.hip", "ae_api.hip"]
-HEADERS = [os.path.join(CSRC, "ae_internal.h"), os.path.join(CSRC, "ae_device.h"), os.path.join(ROOT, "include", "aemodel.h")]
+SOURCES = ["ae_plan.cpp", "ae_elem.hip", "ae_noise.hip", "ae_conv_direct.hip", "ae_conv_mfma.hip", "ae_conv_thin.hip", "ae_conv_thin_mfma.hip", "ae_calib.hip", "ae_mx.hip", "ae_affine.hip", "ae_fold.hip", "ae_fused_small.hip", "ae_api.hip"]
+HEADERS = [os.path.join(CSRC, "ae_internal.h"), os.path.join(CSRC, "ae_device.h"), os.path.join(CSRC, "ae_philox.h"), os.path.join(ROOT, "include", "aemodel.h")]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-ffp-contract=off", "-fhip-fp32-correctly-rounded-divide-sqrt", "-Wall", "-Wno-unused-function",

@@ -595,32 +595,44 @@ hipStream_t lu_side_stream() {
   return side;
 }
 
-// A second branch of work beside the caller's stream: begin() forks the library's stream from `main` (events are per
-// call, so calls from several host threads only share the stream), end() joins it back — also after an error, so that
-// `main` always covers both branches.  Disabled (or no stream to be had): side == main, everything stays in order.
+// A second branch of work beside the caller's stream: begin() forks the library's stream from `main`, end() joins it
+// back — also after an error, so that `main` always covers both branches.  The two events are created once per host
+// thread and reused by every call (a wait enqueued on a stream refers to the record that preceded it, so recording
+// the event again for the next call does not disturb waits already enqueued); calls from several host threads only
+// share the stream.  Disabled (or no stream / events to be had): side == main, everything stays in order.
 struct SideBranch {
   hipStream_t main = nullptr, side = nullptr;
   hipEvent_t fork = nullptr, join = nullptr;
+  static bool events(hipEvent_t* f, hipEvent_t* j) {
+    static thread_local hipEvent_t ev[2] = {nullptr, nullptr};
+    static thread_local bool tried = false;
+    if (!tried) {
+      tried = true;
+      if (hipEventCreateWithFlags(&ev[0], hipEventDisableTiming) != hipSuccess) ev[0] = nullptr;
+      if (ev[0] && hipEventCreateWithFlags(&ev[1], hipEventDisableTiming) != hipSuccess) {
+        (void)hipEventDestroy(ev[0]);
+        ev[0] = ev[1] = nullptr;
+      }
+    }
+    *f = ev[0];
+    *j = ev[1];
+    return ev[0] != nullptr;
+  }
   int begin(hipStream_t s, bool enable, const char* who) {
     main = side = s;
     hipStream_t s2 = enable ? lu_side_stream() : nullptr;
-    if (!s2) return AE_OK;
-    if (hipEventCreateWithFlags(&fork, hipEventDisableTiming) != hipSuccess) { fork = nullptr; return fail(AE_EHIP, "%s: cannot create an event", who); }
-    if (hipEventCreateWithFlags(&join, hipEventDisableTiming) != hipSuccess || hipEventRecord(fork, s) != hipSuccess ||
-        hipStreamWaitEvent(s2, fork, 0) != hipSuccess) {
-      (void)hipEventDestroy(fork);
-      if (join) (void)hipEventDestroy(join);
-      fork = join = nullptr;
+    hipEvent_t f = nullptr, j = nullptr;
+    if (!s2 || !events(&f, &j)) return AE_OK;
+    if (hipEventRecord(f, s) != hipSuccess || hipStreamWaitEvent(s2, f, 0) != hipSuccess)
       return fail(AE_EHIP, "%s: cannot fork the side stream", who);
-    }
+    fork = f;
+    join = j;
     side = s2;
     return AE_OK;
   }
   int end(int rc, const char* who) {
     if (!fork) return rc;
     const bool joined = hipEventRecord(join, side) == hipSuccess && hipStreamWaitEvent(main, join, 0) == hipSuccess;
-    (void)hipEventDestroy(fork);                // (released by the runtime once the recorded work has completed)
-    (void)hipEventDestroy(join);
     fork = join = nullptr;
     if (!joined && rc == AE_OK) rc = fail(AE_EHIP, "%s: cannot join the side stream", who);
     return rc;
@@ -746,6 +758,29 @@ __global__ __launch_bounds__(256) void k_qr_skew(const float* __restrict__ g, fl
     const int r = r0 + ty + 8 * j, c = c0 + tx;
     out[(int64_t)r * d + c] = scale * (g[(int64_t)r * d + c] - tile[tx][ty + 8 * j]);
   }
+}
+
+// rowsum[i] = sum_j |m[i][j]|: one wavefront per row, fixed order
+__global__ __launch_bounds__(256) void k_row_abs_sum(const float* __restrict__ m, int d, float* __restrict__ rowsum) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (row >= d) return;
+  float acc = 0.0f;
+  for (int j = lane; j < d; j += 64) acc += fabsf(m[(int64_t)row * d + j]);
+  acc = wave_sum(acc);
+  if (lane == 0) rowsum[row] = acc;
+}
+// out[0] = max_i v[i] (one workgroup; NaN propagates as +inf so that the caller refuses it)
+__global__ __launch_bounds__(256) void k_vec_max(const float* __restrict__ v, int d, float* __restrict__ out) {
+  __shared__ float sm[256];
+  float mx = 0.0f;
+  for (int i = threadIdx.x; i < d; i += 256) { const float x = v[i]; mx = (x == x) ? fmaxf(mx, x) : INFINITY; }
+  sm[threadIdx.x] = mx;
+  __syncthreads();
+  for (int off = 128; off > 0; off >>= 1) {
+    if ((int)threadIdx.x < off) sm[threadIdx.x] = fmaxf(sm[threadIdx.x], sm[threadIdx.x + off]);
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) out[0] = sm[0];
 }
 
 // acc = (first ? 0 : acc) + alpha * y
@@ -935,6 +970,30 @@ extern "C" int model_qr_workspace(int64_t d, int squarings, int64_t* bytes) {
   if (!bytes) return fail(AE_EINVAL, "model_qr_workspace: null argument");
   AE_TRY(check_qr_args("model_qr_workspace", d, AE_F32, squarings));
   *bytes = QrSlots::count(squarings) * d * d * 4 + 1024;
+  return AE_OK;
+}
+
+extern "C" int model_qr_squarings(const float* g, int64_t d, void* workspace, int* squarings, void* stream) {
+  using namespace ae;
+  if (!g || !workspace || !squarings) return fail(AE_EINVAL, "model_qr_squarings: null argument");
+  AE_TRY(check_qr_args("model_qr_squarings", d, AE_F32, 0));
+  if ((reinterpret_cast<uintptr_t>(workspace) & 15) != 0) return fail(AE_EINVAL, "model_qr_squarings: the workspace must be 16-byte aligned");
+  hipStream_t s = (hipStream_t)stream;
+  const int n = (int)d;
+  float* skew = reinterpret_cast<float*>(workspace);          // S = (G - G^T) / 2
+  float* rowsum = skew + d * d;                               // then d row sums and the maximum
+  hipLaunchKernelGGL(k_qr_skew, dim3(n / 32, n / 32), dim3(256), 0, s, g, 0.5f, n, skew);
+  hipLaunchKernelGGL(k_row_abs_sum, dim3((n + 3) / 4), dim3(256), 0, s, (const float*)skew, n, rowsum);
+  hipLaunchKernelGGL(k_vec_max, dim3(1), dim3(256), 0, s, (const float*)rowsum, n, rowsum + d);
+  AE_TRY(launch_status("qr_squarings"));
+  float norm = 0.0f;
+  AE_HIP(hipMemcpyAsync(&norm, rowsum + d, sizeof(float), hipMemcpyDeviceToHost, s));
+  AE_HIP(hipStreamSynchronize(s));
+  if (!(norm < INFINITY)) return fail(AE_EINVAL, "model_qr_squarings: the generator holds a NaN or an infinity");
+  int j = 0;
+  while (j <= 16 && ldexpf(1.0f, j) < 2.0f * norm) ++j;       // ||S||_2 <= ||S||_inf for a skew-symmetric S
+  if (j > 16) return fail(AE_EINVAL, "model_qr_squarings: ||(G - G^T)/2|| = %g needs more than 16 squarings", (double)norm);
+  *squarings = j;
   return AE_OK;
 }
 

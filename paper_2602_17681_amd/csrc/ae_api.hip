@@ -61,6 +61,9 @@ struct ae_model {
   uint64_t first_sample = 0;
   bool have_forward = false;
   bool packed_in_batch = false;     // the current pass repacked all its weights with one launch
+  bool inference = false;           // forward passes keep nothing for a backward pass (model_set_inference)
+  bool fused_small = false;         // the plan has the shape of the three-launch small-image path
+  ae::FusedSmall fused;
   bool params_static = false;       // the caller promises unchanged parameters: repack only once per direction
   const void* fwd_packed = nullptr; // parameter blob whose forward / input-gradient packing is still valid
   const void* bwd_packed = nullptr;
@@ -565,6 +568,7 @@ int model_create(const char* layer_spec, int batch, int dtype, int bn_mode, ae_m
   m->wgrad_ws = (float*)(m->ws + P.off_wgrad);
   m->wgrad_ws_inorder = (float*)(m->ws + P.off_wgrad_inorder);
   m->splitk_ws = (float*)(m->ws + P.off_splitk);
+  m->fused_small = fused_small_match(P, &m->fused);
   *out = m;
   return AE_OK;
 }
@@ -596,6 +600,13 @@ int model_timing_enable(ae_model* m, int on) {
 int model_set_overlap(ae_model* m, int on) {
   if (!m) return fail(AE_EINVAL, "model_set_overlap: null model");
   m->overlap = on != 0;
+  return AE_OK;
+}
+
+int model_set_inference(ae_model* m, int on) {
+  if (!m) return fail(AE_EINVAL, "model_set_inference: null model");
+  m->inference = on != 0;
+  m->have_forward = false;
   return AE_OK;
 }
 
@@ -676,6 +687,14 @@ int model_forward(ae_model* m, const void* params, const void* x, float snr_db, 
   const float sigma = (float)pow(10.0, -(double)snr_db / 20.0);
   m->have_forward = false;
   const size_t ns = P.steps.size();
+  if (m->inference && m->fused_small) {
+    // small-image network, nothing to keep: three launches (see ae_fused_small.hip)
+    const double io = ((double)P.batch * (P.c0 * P.h0 * P.w0 + P.cl * P.hl * P.wl) + (double)P.n_params) * 4.0;
+    TIMED(0, "fwd.fused_small", 0.0, io,
+          launch_fused_small(P, m->fused, prm, (const float*)x, (float*)y, (float*)P.steps[0].raw, (float*)P.steps[1].raw,
+                             m->partial, sigma, seed, m->first_sample, s));
+    return AE_OK;
+  }
   AE_TRY(join_pack(m, s, true));
   if (m->params_static && m->fwd_packed == params) {
     m->packed_in_batch = true;     // the packed copies of an earlier call are still valid
@@ -711,7 +730,7 @@ int model_forward(ae_model* m, const void* params, const void* x, float snr_db, 
     AE_HIP(hipMemcpyAsync(y, st.out, bytes, hipMemcpyDeviceToDevice, s));
   }
   AE_TRY(join_pack(m, s, true));
-  m->have_forward = true;
+  m->have_forward = !m->inference;
   return AE_OK;
 }
 

@@ -94,6 +94,16 @@ struct Plan {
 
 int build_plan(const char* spec, int batch, int dtype, int bn_mode, Plan* plan);
 
+// The three-launch forward path for small-image networks (ae_fused_small.hip): parameter offsets and channel
+// counts of the matched plan.
+struct FusedSmall {
+  int64_t w1, b1, bn1, w2, b2, bn2, wf1, bf1, wf2, bf2, w3, b3, w4, b4;
+  int c1, c2, n, cr, c3, c4;
+};
+bool fused_small_match(const Plan& P, FusedSmall* f);
+int launch_fused_small(const Plan& P, const FusedSmall& f, const float* params, const float* x, float* y, float* raw1,
+                       float* raw2, float* partial, float sigma, uint64_t seed, uint64_t first_sample, hipStream_t s);
+
 // Rows of a column reduction handled by one block (partial-sum granularity): 256 for
 // large tensors, fewer when that would leave the machine with too few blocks.
 constexpr int kReduceRows = 256;

@@ -393,6 +393,37 @@ def test_qr_polynomial_order_at_the_documented_limit(ae):
     assert _close(a5, ref, TOL["f32"]), np.abs(a5 - ref).max()
 
 
+def test_qr_squarings_from_the_generator_norm(ae):
+    """model_qr_squarings gives the smallest J with 2^J >= 2 ||S||_inf (a bound of the spectral norm); composing a
+    generator of unknown size with that J meets the binary32 bar, and a NaN in the generator is refused."""
+    import torch
+    d = 128
+    for scale in (0.01, 1.0, 40.0):
+        params = wl.make_qr_params(d, seed=23)
+        params = ((params[0] * scale).astype(np.float32),) + tuple(params[1:])
+        g = params[0].astype(np.float64)
+        s = (g - g.T) / 2.0
+        ninf = np.abs(s).sum(axis=1).max()
+        want = 0
+        while 2.0 ** want < 2.0 * ninf:
+            want += 1
+        ws = torch.empty(ae.model_qr_workspace(d, 0), dtype=torch.uint8, device="cuda")
+        j = ae.model_qr_squarings(torch.from_numpy(params[0]).cuda(), d, ws)
+        assert abs(j - want) <= (1 if abs(np.log2(2.0 * ninf) - round(np.log2(2.0 * ninf))) < 1e-4 else 0), (j, want)
+        assert 2.0 ** j >= 2.0 * np.linalg.norm(s, 2)
+        a, = _qr_run(ae, params, d, "f32", squarings=j)
+        ref = ao.qr_compose(*params)
+        assert _close(a, ref, 1e-3 if scale > 10 else TOL["f32"]), np.abs(a - ref).max()
+    bad = torch.zeros((d, d), device="cuda")
+    bad[3, 5] = float("nan")
+    with pytest.raises(ae.AeError):
+        ae.model_qr_squarings(bad, d, ws)
+    huge = torch.zeros((d, d), device="cuda")
+    huge[0, 1] = 1e6
+    with pytest.raises(ae.AeError):
+        ae.model_qr_squarings(huge, d, ws)
+
+
 def test_qr_argument_checks(ae):
     import torch
     t = torch.zeros(64 * 64, device="cuda")

@@ -185,6 +185,72 @@ def test_cfg1_forward_backward_perturbed(ae):
     run_case(cfg["spec"], 16, dtype="f32", seed=cfg["seed"], snr_db=10.0, backward=True, perturb=True)
 
 
+SMALL_IMAGE = [
+    (None, 64),                       # cfg1 itself
+    ("in:3x16x24,conv3:16,bn,relu,pool2,conv3:48,bn,relu,pool2,flatten,fc:22,pnorm,awgn,fc:768,reshape:32x4x6,"
+     "up2,conv3:32,relu,up2,conv3:3,sigmoid", 9),
+    ("in:4x32x32,conv3:32,bn,relu,pool2,conv3:16,bn,relu,pool2,flatten,fc:256,pnorm,awgn,fc:1024,reshape:16x8x8,"
+     "up2,conv3:32,relu,up2,conv3:4,sigmoid", 300),
+]
+
+
+@pytest.mark.parametrize("case", range(len(SMALL_IMAGE)))
+def test_inference_mode_small_image_path(ae, case):
+    """A model in inference mode runs small-image networks of cfg1's shape in three launches (one workgroup per
+    sample, tensors in LDS): y against the oracle at 1e-4 and against the layer-by-layer path of the same library;
+    nothing is kept for a backward pass."""
+    import torch
+    spec, batch = SMALL_IMAGE[case]
+    spec = spec or wl.CONFIGS["cfg1"]["spec"]
+    params = wl.make_params(spec, 50 + case, perturb=True)
+    x = wl.make_input(spec, batch, 50 + case)
+    first = (1 << 32) - 3
+    y_ref = orc.Net(spec, batch).forward(params, x, snr_db=7.0, seed=50 + case, first_sample=first)
+    m = ae.Model(spec, batch)
+    pd, xd = torch.from_numpy(params).cuda(), torch.from_numpy(x).cuda()
+    ys = []
+    for k, inference in enumerate((False, True, True)):
+        m.model_set_inference(inference)
+        m.model_timing_reset()
+        m.model_timing_enable(k == 1)
+        y = torch.full((batch,) + m.out_shape, float("nan"), device="cuda")
+        m.model_set_sample_offset(first)
+        m.model_forward(pd, xd, 7.0, 50 + case, y)
+        ys.append(y.cpu().numpy())
+        assert_close(ys[-1], y_ref, 1e-4, "y (inference=%s)" % inference)
+        if k == 1:      # the pass really took the three-launch path: its one timing slot saw the launch
+            assert [t["name"] for t in m.model_timing_read() if t["launches"]] == ["step00.fwd.fused_small"]
+    m.model_timing_enable(False)
+    assert np.array_equal(ys[1], ys[2])
+    assert_close(ys[1], ys[0], 2e-5, "three-launch path against the layer-by-layer path")
+    g = torch.zeros(m.n_params, device="cuda")
+    with pytest.raises(ae.AeError) as e:
+        m.model_backward(pd, xd, torch.zeros_like(y), g)
+    assert e.value.code == -4
+    with pytest.raises(ae.AeError) as e:
+        m.model_get_activation(0, torch.zeros((batch,) + m.model_step_info(0)[1], device="cuda"))
+    assert e.value.code == -4
+    m.model_set_inference(False)
+    m.model_forward(pd, xd, 7.0, 50 + case, y)
+    m.model_backward(pd, xd, torch.zeros_like(y), g)        # training mode again: backward works
+    m.close()
+
+
+def test_inference_mode_of_a_network_without_a_fused_path(ae):
+    """Inference mode changes nothing for a network that has no special path: same bits as the default mode."""
+    import torch
+    spec = "in:10x1x1,fc:33,relu,fc:16,pnorm,awgn,fc:20,relu,fc:10,sigmoid"
+    m = ae.Model(spec, 67)
+    pd = torch.from_numpy(wl.make_params(spec, 3, perturb=True)).cuda()
+    xd = torch.from_numpy(wl.make_input(spec, 67, 3)).cuda()
+    y0, y1 = torch.empty((67, 10, 1, 1), device="cuda"), torch.empty((67, 10, 1, 1), device="cuda")
+    m.model_forward(pd, xd, 3.0, 3, y0)
+    m.model_set_inference(True)
+    m.model_forward(pd, xd, 3.0, 3, y1)
+    assert torch.equal(y0, y1)
+    m.close()
+
+
 @pytest.mark.parametrize("snr_db", [0.0, 20.0])
 def test_cfg2_reduced_resolution(ae, snr_db):
     spec = wl.scaled_spec("cfg2", 16)
@@ -431,10 +497,12 @@ def test_calibration_loop_and_its_argument_checks(ae):
 
 
 # ------------------------------------------------------------------ full benchmark sizes
-def test_cfg2_full_size_forward_backward(ae):
-    """cfg2 exactly as bench.py runs it (batch 256, 3x32x32, fp32), every activation and gradient."""
+@pytest.mark.parametrize("snr_db", wl.CONFIGS["cfg2"]["snr_db"])
+def test_cfg2_full_size_forward_backward(ae, snr_db):
+    """cfg2 exactly as bench.py runs it (batch 256, 3x32x32, fp32) at each SNR point of its sweep: every activation
+    and every gradient of the training step."""
     cfg = wl.CONFIGS["cfg2"]
-    run_case(cfg["spec"], cfg["batch"], dtype="f32", seed=cfg["seed"], snr_db=5.0, perturb=False, flips=True)
+    run_case(cfg["spec"], cfg["batch"], dtype="f32", seed=cfg["seed"], snr_db=snr_db, perturb=False, flips=True, cot="mse")
 
 
 FULL_SIZE_LINEAR = [
