@@ -70,10 +70,23 @@ struct IgemmParams {
   // tri_d > 0 (modes 8, 9): the matrices are an identity block beyond row and column tri_d; tiles of the odd block that
   // lie wholly beyond it return (their outputs are zero and stay unwritten) and K ranges over the odd block end at tri_d.
   int tri, tri_b, tri_d;
+  // k_conv3_patch on images wider than its tile: a tile is TH rows x Wt columns of one of `strips` column strips
+  // of the image (Wt = Wc / strips, TH = 256 / Wt); GEMM row m = tile * 256 + th * Wt + tw then is pixel
+  // (row block * TH + th, strip * Wt + tw) of its image.  1: a tile spans the image width and rows are pixels in order.
+  int strips = 1;
 };
 
 // output row (pixel index in y) of GEMM row m
 __device__ __forceinline__ int64_t igemm_out_row(const IgemmParams& p, int64_t m, int phase) {
+  if (p.strips > 1) {
+    const unsigned mu = (unsigned)m, wt = (unsigned)(p.Wc / p.strips), th_n = 256u / wt;
+    const unsigned ml = mu & 255u, tile = mu >> 8;
+    const unsigned tw = ml % wt, th = ml / wt;
+    const unsigned strip = tile % (unsigned)p.strips, t2 = tile / (unsigned)p.strips;
+    const unsigned blocks = (unsigned)p.Hc / th_n;
+    const unsigned rb = t2 % blocks, img = t2 / blocks;
+    return ((int64_t)img * p.Hc + rb * th_n + th) * p.Wc + strip * wt + tw;
+  }
   if (p.phases == 1) return m;
   const unsigned mu = (unsigned)m;
   const unsigned j = mu % (unsigned)p.Wc, t = mu / (unsigned)p.Wc;
@@ -159,8 +172,8 @@ __device__ __forceinline__ void igemm_store_interior(const floatx16 (&acc)[MI][N
     for (int c = 0; c < (32 * CPRO) / 64; ++c) {
       const int idx = c * 64 + lane;
       const int lr = idx / CPRO, ch = idx % CPRO;
-      T* dst = p.phases == 1 ? yrow + (int64_t)(i * 32 + lr) * N + ch * EPC
-                             : ycol + igemm_out_row(p, mrow0 + i * 32 + lr, phase) * N + ch * EPC;
+      T* dst = (p.phases == 1 && p.strips == 1) ? yrow + (int64_t)(i * 32 + lr) * N + ch * EPC
+                                                : ycol + igemm_out_row(p, mrow0 + i * 32 + lr, phase) * N + ch * EPC;
       if constexpr (MXQ) {
         // MX block quantisation of the stored row: a block of mx_block columns is mx_block/EPC neighbouring lanes of this
         // pass (a staged row is CPRO >= mx_block/EPC consecutive lanes, blocks do not straddle rows)
@@ -753,8 +766,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   const int64_t m0 = (int64_t)tile_m * BM;
   const int n0 = tile_n * BN;
   const int tiles_per_img = p.Hc / TH;
-  const int img = tile_m / tiles_per_img;
-  const int h0 = (tile_m - img * tiles_per_img) * TH;
+  const int strip = tile_m % p.strips, row_tile = tile_m / p.strips;   // (strips = 1: the tile spans the image width)
+  const int img = row_tile / tiles_per_img;
+  const int h0 = (row_tile - img * tiles_per_img) * TH;
+  const int w0 = strip * W;
   const int Hin = p.Hc >> p.up, Win = p.Wc >> p.up;
   const __amdgpu_buffer_rsrc_t rX = make_rsrc(p.x, p.x_bytes);
   const __amdgpu_buffer_rsrc_t rW = make_rsrc(p.w, p.w_bytes);
@@ -767,8 +782,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
     const int cell = q >> 2;
     const int chunk = (q & 3) ^ ((cell >> 2) & 3);
     const int pr = cell / PW, pc = cell - pr * PW;
-    const int hh = h0 - 1 + pr, ww = pc - 1;
-    const bool ok = cell < PC && hh >= 0 && hh < p.Hc && ww >= 0 && ww < W;
+    const int hh = h0 - 1 + pr, ww = w0 + pc - 1;
+    const bool ok = cell < PC && hh >= 0 && hh < p.Hc && ww >= 0 && ww < p.Wc;
     const unsigned pix = ((unsigned)img * (unsigned)Hin + (unsigned)(hh >> p.up)) * (unsigned)Win + (unsigned)(ww >> p.up);
     a_off[i] = ok ? pix * (unsigned)(p.Cin * ES) + (unsigned)chunk * 16u : kOob;
   }
@@ -934,8 +949,10 @@ bool conv_mfma_supported(const ConvArgs& a0) {
 // epilogue needs no run-time checks.
 static bool conv3_patch_usable(const ConvArgs& a) {
   if (a.geom != CONV_PLAIN || a.k != 3 || !conv_mfma_supported(a)) return false;
-  if (a.wc != 16 && a.wc != 32 && a.wc != 64) return false;   // W = 128 needs 96 KB of LDS: one workgroup per compute unit, slower
-  const int th = 256 / a.wc;
+  // (a 128-pixel-wide tile would need 96 KB of LDS, one workgroup per compute unit: wider images are cut into column
+  // strips of 64 pixels instead, whose halo columns come from the neighbouring strip)
+  if (a.wc != 16 && a.wc != 32 && a.wc != 64 && a.wc != 128 && a.wc != 256) return false;
+  const int th = 256 / (a.wc > 64 ? 64 : a.wc);
   if (a.hc % th != 0 || a.cout % 64 != 0) return false;
   const int bn = a.cout % 128 == 0 ? 128 : 64;
   const int64_t tiles = ((int64_t)a.n * a.hc * a.wc / 256) * (a.cout / bn);
@@ -1044,6 +1061,7 @@ int launch_conv_mfma(const ConvArgs& a0, hipStream_t s) {
   if (conv3_patch_usable(a0)) {
     const int bn = a.cout % 128 == 0 ? 128 : 64;
     p.tiles_n = a.cout / bn;
+    p.strips = a.wc > 64 ? a.wc / 64 : 1;
     dim3 pgrid((unsigned)((p.M / 256) * p.tiles_n));
 #define PATCH_LAUNCH_W(T, WV)                                                                             \
   do {                                                                                                   \

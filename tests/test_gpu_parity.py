@@ -515,6 +515,10 @@ FULL_SIZE_LINEAR = [
     # both forms of an upsampled conv at a size where the forward takes the four-phase form without
     # split-K (4 phases x 128 tiles) and the input gradient runs as one launch of 256 tiles
     ("in:64x32x32,conv3:256,up2,conv3:64", 32, "bf16"),
+    # images wider than the 64-pixel tile of the LDS-patch kernel: column strips with halo columns from the neighbour
+    # (fp32; 128 and 256 wide, a height that is not a power of two)
+    ("in:16x128x128,conv3:64,conv3:64", 4, "f32"),
+    ("in:32x12x256,conv3:64,relu,conv3:128", 24, "bf16"),
 ]
 
 
