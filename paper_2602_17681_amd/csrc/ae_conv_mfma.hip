@@ -952,6 +952,10 @@ static bool conv3_patch_usable(const ConvArgs& a) {
   // (a 128-pixel-wide tile would need 96 KB of LDS, one workgroup per compute unit: wider images are cut into column
   // strips of 64 pixels instead, whose halo columns come from the neighbouring strip)
   if (a.wc != 16 && a.wc != 32 && a.wc != 64 && a.wc != 128 && a.wc != 256) return false;
+  // (measured on the 128 x 128 layers of the largest workload: with four channel slabs the strip form beats the per-tap
+  // kernel, 98 against 109 us; with two slabs the patch of the second slab is all there is to prefetch behind the
+  // first, and the per-tap kernel wins, 111 against 135 us)
+  if (a.wc > 64 && a.cin * (int)dtype_size(a.dtype) < 256) return false;
   const int th = 256 / (a.wc > 64 ? 64 : a.wc);
   if (a.hc % th != 0 || a.cout % 64 != 0) return false;
   const int bn = a.cout % 128 == 0 ? 128 : 64;
@@ -1554,9 +1558,9 @@ struct Wgrad3 {
   static constexpr int cell_base(int ks) { return ((ks * 16) / SW) * PCW + (ks * 16) % SW; }
 };
 
-// fragments of one K-step: MI of dY, three (taps) of the patch
-template <int BM, int SW, int KS>
-__device__ __forceinline__ void wgrad3_reads(TrFrag (&fa)[BM / 64], TrFrag (&fb)[3], unsigned a_addr, const unsigned (&b_addr)[3]) {
+// fragments of one K-step: MI of dY, NTAP (taps) of the patch
+template <int BM, int SW, int KS, int NTAP>
+__device__ __forceinline__ void wgrad3_reads(TrFrag (&fa)[BM / 64], TrFrag (&fb)[NTAP], unsigned a_addr, const unsigned (&b_addr)[NTAP]) {
   typedef Wgrad3<BM, SW> G;
 #pragma unroll
   for (int i = 0; i < G::MI; ++i) {
@@ -1565,23 +1569,34 @@ __device__ __forceinline__ void wgrad3_reads(TrFrag (&fa)[BM / 64], TrFrag (&fb)
     else tr_read<KS * 16 * G::RBA>(fa[i], a_addr ^ 64u, 4 * G::RBA);
   }
 #pragma unroll
-  for (int s_ = 0; s_ < 3; ++s_) tr_read<G::cell_base(KS) * 128>(fb[s_], b_addr[s_], 4 * 128);
+  for (int s_ = 0; s_ < NTAP; ++s_) tr_read<G::cell_base(KS) * 128>(fb[s_], b_addr[s_], 4 * 128);
 }
 
-template <int BM, int SW>
+// UP2: the convolution reads its input through a x2 nearest-neighbour upsample.  An output pixel (2i+a, 2j+b) then
+// sees only 2 x 2 distinct stored pixels, (i + u - (1-a), j + v - (1-b)), u, v in {0,1}, and the nine taps fall onto
+// them: r -> u = (a == 0 ? r > 0 : r > 1), s -> v likewise.  So the kernel forms, per output parity (a, b), the four
+// correlations of that phase's quarter of dY with the shifted stored input — 16 tap matrices of a quarter of the
+// pixels each, 4/9 of the multiply-adds — and k_wgrad_reduce_up2 adds, for every weight (r, s), the four phase
+// matrices it belongs to (exact in real arithmetic; every product is of the same bf16 values as in the plain form).
+// A workgroup owns (a, b, u) and the two taps v = 0, 1: a slab is 64 pixels of one phase (every other pixel of every
+// other dY row, gathered by the global-to-LDS load), the patch is a row of the STORED image with its halo, and SW,
+// Hc, Wc, M below are those of the stored image.
+template <int BM, int SW, bool UP2>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k_wgrad_row3(WgradParams p) {
   typedef Wgrad3<BM, SW> G;
   constexpr int MI = G::MI;
+  constexpr int NTAP = UP2 ? 2 : 3;
   __shared__ __attribute__((aligned(1024))) char smem[3 * G::STAGE];   // XOR address arithmetic below needs the alignment
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   int b = xcd_logical_block((int)blockIdx.x, (int)gridDim.x);
-  const int r = b % 3; b /= 3;
+  const int r = b % (UP2 ? 8 : 3); b /= (UP2 ? 8 : 3);      // UP2: r = (a, b, u) as three bits
+  const int par_a = (r >> 2) & 1, par_b = (r >> 1) & 1, par_u = r & 1;
   const int tn = b % p.tiles_n; b /= p.tiles_n;
   const int tm = b % p.tiles_m;
   const int split = b / p.tiles_m;
   const int co0 = tm * BM, ci0 = tn * 64;
-  const int Hin = p.Hc >> p.up, Win = p.Wc >> p.up;
+  const int Hin = UP2 ? p.Hc : (p.Hc >> p.up), Win = UP2 ? p.Wc : (p.Wc >> p.up);
   const int64_t m_begin = (int64_t)split * p.rows_per_split;
   const int64_t m_end = (m_begin + p.rows_per_split < p.M) ? m_begin + p.rows_per_split : p.M;
   const int KT = (int)((m_end - m_begin) / G::BK);
@@ -1596,7 +1611,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
     const int q = i * 256 + tid;
     const int px = q / CPP, chunk = q % CPP;
     const int sw = G::RBA == 256 ? (px & 3) : ((px >> 1) & 1);
-    a_voff[i] = (unsigned)px * (unsigned)(p.Cout * 2) + (unsigned)(co0 * 2) + (unsigned)((chunk ^ (sw << 2)) * 16);
+    // UP2: slab pixel px = (segment row px / SW, column px % SW) of the stored image is dY pixel (2 row + a, 2 column + b)
+    const unsigned dpx = UP2 ? (unsigned)((px / SW) * 2 * (2 * p.Wc) + (px % SW) * 2) : (unsigned)px;
+    a_voff[i] = dpx * (unsigned)(p.Cout * 2) + (unsigned)(co0 * 2) + (unsigned)((chunk ^ (sw << 2)) * 16);
   }
   // patch: unit u = wave + 4*k of 1 KB: slot q = u*64 + lane: cell q / 8, chunk q % 8
   int x_seg[G::XU], x_pc[G::XU];
@@ -1612,7 +1629,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
     x_cell_ok[k] = cell < G::PCELLS && x_pc[k] >= 1 && x_pc[k] <= SW + 2;
   }
   // coordinates of the next slab to load (uniform)
-  unsigned a_soff = (unsigned)m_begin * (unsigned)(p.Cout * 2);
+  unsigned a_soff = (unsigned)m_begin * (unsigned)(p.Cout * 2);     // (UP2: recomputed from (n, h, w0) per slab)
   int w0 = (int)((unsigned)m_begin % (unsigned)p.Wc);
   int h = (int)(((unsigned)m_begin / (unsigned)p.Wc) % (unsigned)p.Hc);
   int n = (int)((unsigned)m_begin / ((unsigned)p.Wc * (unsigned)p.Hc));
@@ -1620,17 +1637,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
 #define WGRAD3_DMA(STG)                                                                                      \
   {                                                                                                          \
     char* const da = smem + (STG) * G::STAGE + wave * 1024;                                                  \
+    if (UP2) a_soff = (((unsigned)n * (unsigned)(2 * p.Hc) + (unsigned)(2 * h + par_a)) * (unsigned)(2 * p.Wc) + (unsigned)(2 * w0 + par_b)) * (unsigned)(p.Cout * 2); \
     _Pragma("unroll") for (int i = 0; i < G::A_PASSES; ++i)                                                  \
         dma_load16s(rDY, da + i * 4096, a_voff[i], a_soff);                                                  \
     _Pragma("unroll") for (int k = 0; k < G::XU; ++k) {                                                      \
       if (wave + 4 * k < G::X_UNITS) {                                                                       \
-        const int row = h + x_seg[k] + r - 1, col = w0 + x_pc[k] - 2;                                        \
+        const int row = h + x_seg[k] + (UP2 ? par_u + par_a - 1 : r - 1), col = w0 + x_pc[k] - 2;            \
         const bool ok = x_cell_ok[k] && row >= 0 && row < p.Hc && col >= 0 && col < p.Wc;                    \
-        const unsigned pix = ((unsigned)n * (unsigned)Hin + (unsigned)(row >> p.up)) * (unsigned)Win + (unsigned)(col >> p.up); \
+        const unsigned pix = UP2 ? ((unsigned)n * (unsigned)Hin + (unsigned)row) * (unsigned)Win + (unsigned)col        \
+                                 : ((unsigned)n * (unsigned)Hin + (unsigned)(row >> p.up)) * (unsigned)Win + (unsigned)(col >> p.up); \
         dma_load16(rX, smem + (STG) * G::STAGE + G::A_BYTES + (wave + 4 * k) * 1024, ok ? pix * cin_bytes + x_chunk[k] : kOob); \
       }                                                                                                      \
     }                                                                                                        \
-    a_soff += (unsigned)(G::BK * p.Cout * 2);                                                                \
+    if (!UP2) a_soff += (unsigned)(G::BK * p.Cout * 2);                                                      \
     if (SW < 64) { h += G::SR; if (h == p.Hc) { h = 0; ++n; } }                                              \
     else { w0 += 64; if (w0 == p.Wc) { w0 = 0; if (++h == p.Hc) { h = 0; ++n; } } }                          \
   }
@@ -1643,28 +1662,31 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   const int a_col = G::RBA == 256 ? (2 * wm) : wm;                       // 64-byte column of the wave's first 32 channels
   const int a_sw = G::RBA == 256 ? (lp & 3) : ((lp >> 1) & 1);
   const unsigned a_lane = (unsigned)(lp * G::RBA + ((a_col ^ a_sw) << 6) + 32 * (grp & 1) + 8 * (sl & 3));
-  unsigned b_lane[3];
+  unsigned b_lane[NTAP];
 #pragma unroll
-  for (int s_ = 0; s_ < 3; ++s_) {
-    const int cell = 1 + s_ + lp;                // + cell_base(ks) (a multiple of 4) + 4 for the second half
+  for (int s_ = 0; s_ < NTAP; ++s_) {
+    // (UP2: tap v of column parity b reads stored column j + v - (1-b): the view shifted by b + v - 1)
+    // (SW = 8: the 16 pixels of a K-step are two segment rows of the patch, PCW cells apart)
+    const int lp_cell = SW >= 16 ? lp : (lp / SW) * G::PCW + lp % SW;
+    const int cell = 1 + s_ + (UP2 ? par_b : 0) + lp_cell;   // + cell_base(ks) (a multiple of 4) + 4 for the second half
     b_lane[s_] = (unsigned)(G::A_BYTES + cell * 128 + ((wn ^ ((cell >> 1) & 1)) << 6) + 32 * (grp & 1) + 8 * (sl & 3));
   }
 
-  floatx16 acc[3][MI];
+  floatx16 acc[NTAP][MI];
 #pragma unroll
-  for (int s_ = 0; s_ < 3; ++s_)
+  for (int s_ = 0; s_ < NTAP; ++s_)
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[s_][i][e] = 0.0f;
 
-  [[maybe_unused]] TrFrag fa0[MI], fb0[3], fa1[MI], fb1[3];   // (used by the device pass only)
-  [[maybe_unused]] constexpr int NR = 2 * (MI + 3);            // LDS reads per K-step
+  [[maybe_unused]] TrFrag fa0[MI], fb0[NTAP], fa1[MI], fb1[NTAP];   // (used by the device pass only)
+  [[maybe_unused]] constexpr int NR = 2 * (MI + NTAP);               // LDS reads per K-step
 #define WGRAD3_MMA(FA, FB)                                                                                   \
   {                                                                                                          \
     bf16x8 av[MI];                                                                                           \
     _Pragma("unroll") for (int i = 0; i < MI; ++i) av[i] = tr_value(FA[i]);                                  \
-    _Pragma("unroll") for (int s_ = 0; s_ < 3; ++s_) {                                                       \
+    _Pragma("unroll") for (int s_ = 0; s_ < NTAP; ++s_) {                                                    \
       const bf16x8 bv = tr_value(FB[s_]);                                                                    \
       _Pragma("unroll") for (int i = 0; i < MI; ++i)                                                         \
           acc[s_][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv, acc[s_][i], 0, 0, 0);              \
@@ -1679,10 +1701,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   __builtin_amdgcn_s_waitcnt(vm_imm(0));
   __builtin_amdgcn_s_barrier();
   {
-    unsigned ba[3];
+    unsigned ba[NTAP];
 #pragma unroll
-    for (int s_ = 0; s_ < 3; ++s_) ba[s_] = lds0 + b_lane[s_];
-    wgrad3_reads<BM, SW, 0>(fa0, fb0, lds0 + a_lane, ba);
+    for (int s_ = 0; s_ < NTAP; ++s_) ba[s_] = lds0 + b_lane[s_];
+    wgrad3_reads<BM, SW, 0, NTAP>(fa0, fb0, lds0 + a_lane, ba);
   }
   int cur = 0;
   for (int t = 0; t < KT; ++t) {
@@ -1692,22 +1714,22 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
     const int nxt = cur == 2 ? 0 : cur + 1;
     if (t + 2 < KT) { const int st2 = nxt == 2 ? 0 : nxt + 1; WGRAD3_DMA(st2); }
     [[maybe_unused]] const unsigned sa = lds0 + (unsigned)(cur * G::STAGE) + a_lane;
-    unsigned sb[3], nb[3];
+    unsigned sb[NTAP], nb[NTAP];
 #pragma unroll
-    for (int s_ = 0; s_ < 3; ++s_) { sb[s_] = lds0 + (unsigned)(cur * G::STAGE) + b_lane[s_]; nb[s_] = lds0 + (unsigned)(nxt * G::STAGE) + b_lane[s_]; }
+    for (int s_ = 0; s_ < NTAP; ++s_) { sb[s_] = lds0 + (unsigned)(cur * G::STAGE) + b_lane[s_]; nb[s_] = lds0 + (unsigned)(nxt * G::STAGE) + b_lane[s_]; }
     [[maybe_unused]] const unsigned na = lds0 + (unsigned)(nxt * G::STAGE) + a_lane;
 #if defined(__HIP_DEVICE_COMPILE__)
-    wgrad3_reads<BM, SW, 1>(fa1, fb1, sa, sb);
+    wgrad3_reads<BM, SW, 1, NTAP>(fa1, fb1, sa, sb);
     LGKM_WAIT(NR);
     WGRAD3_MMA(fa0, fb0)
-    wgrad3_reads<BM, SW, 2>(fa0, fb0, sa, sb);
+    wgrad3_reads<BM, SW, 2, NTAP>(fa0, fb0, sa, sb);
     LGKM_WAIT(NR);
     WGRAD3_MMA(fa1, fb1)
-    wgrad3_reads<BM, SW, 3>(fa1, fb1, sa, sb);
+    wgrad3_reads<BM, SW, 3, NTAP>(fa1, fb1, sa, sb);
     LGKM_WAIT(NR);
     WGRAD3_MMA(fa0, fb0)
     if (t + 1 < KT) {
-      wgrad3_reads<BM, SW, 0>(fa0, fb0, na, nb);
+      wgrad3_reads<BM, SW, 0, NTAP>(fa0, fb0, na, nb);
       LGKM_WAIT(NR);
     } else {
       LGKM_WAIT(0);
@@ -1720,19 +1742,53 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
 #undef WGRAD3_MMA
 #undef LGKM_WAIT
 
-  // partial[split][co][(r*3 + s)*Cin + ci]
+  // partial[split][co][(r*3 + s)*Cin + ci]   (UP2: [(r*2 + v)*Cin + ci] with r = (a, b, u), K = 16 Cin)
   float* __restrict__ P = p.partial + (int64_t)split * p.Cout * p.K;
   const int col_lane = lane & 31, row_lane = (lane >> 5) * 4;
   const int ci = ci0 + wn * 32 + col_lane;
 #pragma unroll
-  for (int s_ = 0; s_ < 3; ++s_)
+  for (int s_ = 0; s_ < NTAP; ++s_)
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         const int co = co0 + wm * (BM / 2) + i * 32 + (e >> 2) * 8 + row_lane + (e & 3);
-        P[(int64_t)co * p.K + (r * 3 + s_) * p.Cin + ci] = acc[s_][i][e];
+        P[(int64_t)co * p.K + (r * NTAP + s_) * p.Cin + ci] = acc[s_][i][e];
       }
+}
+
+// The same for the phase form of an upsampled convolution: dW[co][ci][r][s] = sum over splits and over the four output
+// parities (a, b) of partial[split][co][((a, b, u_a(r)), v_b(s))][ci], u_0(r) = (r > 0), u_1(r) = (r > 1), v likewise.
+__global__ __launch_bounds__(256) void k_wgrad_reduce_up2(const float* __restrict__ partial, int splits, int Cout, int Cin,
+                                                          float* __restrict__ dw) {
+  __shared__ float sm[4][64];
+  const int64_t total = (int64_t)Cout * 9 * Cin;
+  const int64_t stride = (int64_t)Cout * 16 * Cin;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t i = (int64_t)blockIdx.x * 64 + lane;
+  float acc = 0.0f;
+  int ci = 0, tap = 0, co = 0;
+  if (i < total) {
+    ci = (int)(i % Cin);
+    const int64_t q = i / Cin;
+    tap = (int)(q % 9);
+    co = (int)(q / 9);
+    const int r = tap / 3, s_ = tap % 3;
+    for (int sp = wave; sp < splits; sp += 4) {
+      const float* src = partial + (int64_t)sp * stride + (int64_t)co * 16 * Cin + ci;
+      float t = 0.0f;
+#pragma unroll
+      for (int ab = 0; ab < 4; ++ab) {
+        const int a = ab >> 1, b = ab & 1;
+        const int u = a == 0 ? (r > 0) : (r > 1), v = b == 0 ? (s_ > 0) : (s_ > 1);
+        t += src[((((a << 2) | (b << 1) | u) << 1) | v) * Cin];
+      }
+      acc += t;
+    }
+  }
+  sm[wave][lane] = acc;
+  __syncthreads();
+  if (wave == 0 && i < total) dw[((int64_t)co * Cin + ci) * 9 + tap] = (sm[0][lane] + sm[1][lane]) + (sm[2][lane] + sm[3][lane]);
 }
 
 // dW[co][ci][r][s] = sum over splits of partial[split][co][(r,s,ci)].  A workgroup owns 64
@@ -1764,9 +1820,31 @@ __global__ __launch_bounds__(256) void k_wgrad_reduce(const float* __restrict__ 
 
 struct WgradPlan { int bm, bn, bk, tiles_m, tiles_n, splits, rows_per_split, row3; };   // bk = 0: generic kernel; row3: three taps per workgroup
 
-WgradPlan plan_wgrad(int cout, int cin, int k, int64_t rows, int wc, int es, int hc = 0) {
+WgradPlan plan_wgrad(int cout, int cin, int k, int64_t rows, int wc, int es, int hc = 0, int up = 0) {
   WgradPlan w;
   w.row3 = 0;
+  // an upsampled 3x3 layer in its phase form (row3 = 2): eight groups (a, b, u) of two taps over the stored image
+  const int hs = hc >> 1, ws = wc >> 1;
+  if (es == 2 && k == 3 && up == 1 && hc > 0 && !(hc & 1) && !(wc & 1) && (ws % 64 == 0 || (ws >= 8 && 64 % ws == 0)) &&
+      ((int64_t)hs * ws) % 64 == 0) {
+    w.row3 = 2;
+    w.bm = cout % 128 == 0 ? 128 : 64;
+    w.bn = 64;
+    w.bk = 64;
+    w.tiles_m = cout / w.bm;
+    w.tiles_n = cin / 64;
+    const int64_t prow = rows / 4;                       // pixels of one phase = pixels of the stored image
+    const int64_t groups = (int64_t)w.tiles_m * w.tiles_n * 8;
+    int64_t splits = (512 + groups - 1) / groups;
+    const int64_t max_splits = (prow + 511) / 512;
+    if (splits > max_splits) splits = max_splits;
+    if (splits < 1) splits = 1;
+    int64_t rps = (prow + splits - 1) / splits;
+    rps = (rps + 63) / 64 * 64;
+    w.rows_per_split = (int)rps;
+    w.splits = (int)((prow + rps - 1) / rps);
+    return w;
+  }
   if (es == 2 && k == 3 && hc > 0 && (wc % 64 == 0 || (wc >= 16 && 64 % wc == 0)) && ((int64_t)hc * wc) % 64 == 0) {
     w.row3 = 1;
     w.bm = cout % 128 == 0 ? 128 : 64;
@@ -1819,14 +1897,14 @@ bool wgrad_mfma_supported(const WgradArgs& a) {
 
 int64_t wgrad_mfma_workspace_floats(const WgradArgs& a) {
   const int64_t rows = (int64_t)a.n * a.hc * a.wc;
-  const WgradPlan w = plan_wgrad(a.cout, a.cin, a.k, rows, a.wc, (int)dtype_size(a.dtype), a.hc);
-  return (int64_t)w.splits * a.cout * a.cin * a.k * a.k;
+  const WgradPlan w = plan_wgrad(a.cout, a.cin, a.k, rows, a.wc, (int)dtype_size(a.dtype), a.hc, a.up);
+  return (int64_t)w.splits * a.cout * a.cin * (w.row3 == 2 ? 16 : a.k * a.k);
 }
 
 int launch_wgrad_mfma(const WgradArgs& a, float* workspace, hipStream_t s) {
   if (!wgrad_mfma_supported(a)) return fail(AE_EINVAL, "wgrad_mfma: shape not supported");
   const int64_t rows = (int64_t)a.n * a.hc * a.wc;
-  const WgradPlan w = plan_wgrad(a.cout, a.cin, a.k, rows, a.wc, (int)dtype_size(a.dtype), a.hc);
+  const WgradPlan w = plan_wgrad(a.cout, a.cin, a.k, rows, a.wc, (int)dtype_size(a.dtype), a.hc, a.up);
   WgradParams p;
   // a 1x1 layer that needs no split: the partial layout [co][ci] is the canonical one
   const bool direct = w.splits == 1 && a.k == 1;
@@ -1843,7 +1921,10 @@ int launch_wgrad_mfma(const WgradArgs& a, float* workspace, hipStream_t s) {
     while ((1 << p.log_w) < a.wc) ++p.log_w;
     while ((1 << p.log_h) < a.hc) ++p.log_h;
   }
-  const int64_t blocks = (int64_t)w.splits * w.tiles_m * w.tiles_n * (w.row3 ? 3 : a.k * a.k);
+  if (w.row3 == 2) {     // phase form: the kernel walks the stored image
+    p.M = rows / 4; p.Hc = a.hc / 2; p.Wc = a.wc / 2; p.up = 0; p.K = 16 * a.cin;
+  }
+  const int64_t blocks = (int64_t)w.splits * w.tiles_m * w.tiles_n * (w.row3 == 2 ? 8 : w.row3 ? 3 : a.k * a.k);
   if (blocks > 0x7FFFFFFF) return fail(AE_EINVAL, "wgrad_mfma: grid too large");
   dim3 grid((unsigned)blocks);
 #define WGRAD_LAUNCH_P(T, P2)                                                                           \
@@ -1866,14 +1947,19 @@ int launch_wgrad_mfma(const WgradArgs& a, float* workspace, hipStream_t s) {
     else hipLaunchKernelGGL((k_wgrad_rows<T, 64, 64, BKV>), grid, dim3(256), 0, s, p);                  \
   } while (0)
   if (w.row3) {
-    const int sw = a.wc < 64 ? a.wc : 64;
-#define WGRAD_ROW3(BMV)                                                                                 \
+    const int sw = p.Wc < 64 ? p.Wc : 64;
+#define WGRAD_ROW3(BMV, UPV)                                                                            \
   do {                                                                                                  \
-    if (sw == 64) hipLaunchKernelGGL((k_wgrad_row3<BMV, 64>), grid, dim3(256), 0, s, p);                \
-    else if (sw == 32) hipLaunchKernelGGL((k_wgrad_row3<BMV, 32>), grid, dim3(256), 0, s, p);           \
-    else hipLaunchKernelGGL((k_wgrad_row3<BMV, 16>), grid, dim3(256), 0, s, p);                         \
+    if (sw == 64) hipLaunchKernelGGL((k_wgrad_row3<BMV, 64, UPV>), grid, dim3(256), 0, s, p);           \
+    else if (sw == 32) hipLaunchKernelGGL((k_wgrad_row3<BMV, 32, UPV>), grid, dim3(256), 0, s, p);      \
+    else hipLaunchKernelGGL((k_wgrad_row3<BMV, 16, UPV>), grid, dim3(256), 0, s, p);                    \
   } while (0)
-    if (w.bm == 128) WGRAD_ROW3(128); else WGRAD_ROW3(64);
+    if (w.row3 == 2 && sw == 8) {      // stored images of 8 x 8: the phase form only
+      if (w.bm == 128) hipLaunchKernelGGL((k_wgrad_row3<128, 8, true>), grid, dim3(256), 0, s, p);
+      else hipLaunchKernelGGL((k_wgrad_row3<64, 8, true>), grid, dim3(256), 0, s, p);
+    }
+    else if (w.row3 == 2) { if (w.bm == 128) WGRAD_ROW3(128, true); else WGRAD_ROW3(64, true); }
+    else { if (w.bm == 128) WGRAD_ROW3(128, false); else WGRAD_ROW3(64, false); }
 #undef WGRAD_ROW3
   }
   else if (w.bk && a.dtype == AE_BF16) { if (w.bk == 64) WGRAD_ROWS(bf16_t, 64); else WGRAD_ROWS(bf16_t, 32); }
@@ -1887,8 +1973,11 @@ int launch_wgrad_mfma(const WgradArgs& a, float* workspace, hipStream_t s) {
   if (direct) return AE_OK;
   const int64_t total = (int64_t)a.cout * a.cin * a.k * a.k;
   const int64_t g = (total + 63) / 64;
-  hipLaunchKernelGGL(k_wgrad_reduce, dim3((unsigned)g), dim3(256), 0, s, workspace, w.splits, a.cout, a.cin, a.k * a.k,
-                     a.dw_canonical);
+  if (w.row3 == 2)
+    hipLaunchKernelGGL(k_wgrad_reduce_up2, dim3((unsigned)g), dim3(256), 0, s, workspace, w.splits, a.cout, a.cin, a.dw_canonical);
+  else
+    hipLaunchKernelGGL(k_wgrad_reduce, dim3((unsigned)g), dim3(256), 0, s, workspace, w.splits, a.cout, a.cin, a.k * a.k,
+                       a.dw_canonical);
   return launch_status("wgrad_reduce");
 }
 
