@@ -93,22 +93,24 @@ def kernel_table(st, steps):
         if s["launches"] == 0:
             continue
         avg_ms = s["total_ms"] / s["launches"]
+        share = EXECUTED_SHARE.get(s["name"].split(".")[-1], 1.0)
         rows.append(dict(name=s["name"], avg_ms=avg_ms, ms_per_step=s["total_ms"] / steps,
-                         tflops=(s["flops"] / avg_ms / 1e9) if s["flops"] > 0 and avg_ms > 0 else None,
+                         tflops=(s["flops"] * share / avg_ms / 1e9) if s["flops"] > 0 and avg_ms > 0 else None,
                          gbs=(s["bytes"] / avg_ms / 1e6) if s["bytes"] > 0 and avg_ms > 0 else None,
                          flops=s["flops"], bytes=s["bytes"]))
     return rows
 
 
 FAMILY = {"conv_mfma": "k_igemm", "dgrad_mfma": "k_igemm", "conv_mfma_phases": "k_igemm", "dgrad_mfma_stride2": "k_igemm",
-          "wgrad_mfma": "k_wgrad",
+          "wgrad_mfma": "k_wgrad", "wgrad_mfma_phases": "k_wgrad",
           "conv_thin_in_mfma": "k_thin_in_mfma", "dgrad_thin_mfma": "k_thin_in_mfma"}
 
 
-# A 3x3 convolution behind a x2 upsample runs as four 2x2 phase convolutions (forward) or one 4x4 stride-2
-# convolution (input gradient): 4/9 of the multiply-adds of the definition.  `achieved` counts the algorithmic
-# FLOPs of the definition (2*M*N*K), `achieved_executed` the multiply-adds the kernels really perform.
-EXECUTED_SHARE = {"conv_mfma_phases": 4.0 / 9.0, "dgrad_mfma_stride2": 4.0 / 9.0}
+# A 3x3 convolution behind a x2 upsample runs as four 2x2 phase convolutions (forward), one 4x4 stride-2
+# convolution (input gradient) or sixteen phase-tap correlations (weight gradient): 4/9 of the multiply-adds of the
+# definition.  The library's slots carry the algorithmic FLOPs of the definition (2*M*N*K); the share below turns
+# them into the multiply-adds the kernels really perform (per-kernel `tflops` in the line are executed rates).
+EXECUTED_SHARE = {"conv_mfma_phases": 4.0 / 9.0, "dgrad_mfma_stride2": 4.0 / 9.0, "wgrad_mfma_phases": 4.0 / 9.0}
 
 
 _MEASURED = {}

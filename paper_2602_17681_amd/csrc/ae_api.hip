@@ -461,7 +461,9 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
   wa.n = P.batch; wa.hc = st.hc; wa.wc = st.wc; wa.cin = st.cin; wa.cout = st.cout; wa.k = st.k; wa.up = st.up;
   wa.dtype = P.dtype;
   if (wgrad_mfma_supported(wa)) {
-    TIMED_ON(ws, si, "bwd.wgrad_mfma", conv_flops, (in_el + raw_el) * es + wel * 4, launch_wgrad_mfma(wa, wws, ws));
+    // (slot FLOPs are the algorithmic ones of the definition; the phase form of an upsampled layer, named apart, executes 4/9 of them)
+    TIMED_ON(ws, si, wgrad_mfma_up_phases(wa) ? "bwd.wgrad_mfma_phases" : "bwd.wgrad_mfma", conv_flops,
+             (in_el + raw_el) * es + wel * 4, launch_wgrad_mfma(wa, wws, ws));
   } else {
     TIMED_ON(ws, si, "bwd.wgrad_zero", 0.0, wel * 4, launch_fill_zero(grads + st.w_off, (int64_t)wel * 4, ws));
     TIMED_ON(ws, si, "bwd.wgrad_direct", conv_flops, (in_el + raw_el) * es + wel * 4, launch_wgrad_direct(wa, ws));

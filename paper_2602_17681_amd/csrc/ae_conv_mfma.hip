@@ -1895,6 +1895,12 @@ bool wgrad_mfma_supported(const WgradArgs& a) {
   return rows < 0x7FFFFFFF;
 }
 
+// does launch_wgrad_mfma run this layer in the phase form of an upsampled convolution (4/9 of the multiply-adds)?
+bool wgrad_mfma_up_phases(const WgradArgs& a) {
+  if (!wgrad_mfma_supported(a)) return false;
+  return plan_wgrad(a.cout, a.cin, a.k, (int64_t)a.n * a.hc * a.wc, a.wc, (int)dtype_size(a.dtype), a.hc, a.up).row3 == 2;
+}
+
 int64_t wgrad_mfma_workspace_floats(const WgradArgs& a) {
   const int64_t rows = (int64_t)a.n * a.hc * a.wc;
   const WgradPlan w = plan_wgrad(a.cout, a.cin, a.k, rows, a.wc, (int)dtype_size(a.dtype), a.hc, a.up);

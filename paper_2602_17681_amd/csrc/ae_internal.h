@@ -198,6 +198,7 @@ struct WgradArgs {
 };
 int launch_wgrad_direct(const WgradArgs& a, hipStream_t s);
 bool wgrad_mfma_supported(const WgradArgs& a);
+bool wgrad_mfma_up_phases(const WgradArgs& a);   // will it run as the phase form of an upsampled conv (4/9 of the multiply-adds)?
 int64_t wgrad_mfma_workspace_floats(const WgradArgs& a);
 int launch_wgrad_mfma(const WgradArgs& a, float* workspace, hipStream_t s);  // overwrites dw (no zeroing needed)
 
