@@ -702,6 +702,9 @@ def main():
     ap.add_argument("--no-overlap", action="store_true",
                     help="keep every kernel of the backward pass on one stream (for per-kernel profiles: with the "
                          "default two streams the weight-gradient kernels share the chip with other kernels)")
+    ap.add_argument("--no-recompute", action="store_true",
+                    help="store the first layer's convolution output instead of recomputing it in every pass that needs it "
+                         "(model_set_recompute(0)): the library's behaviour for layers that have no recomputing path")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="only run a plain device-to-device copy of MIB MiB five times (reference for the "
                          "FETCH_SIZE / WRITE_SIZE counters of rocprofv3) and exit")
@@ -810,6 +813,8 @@ def main():
     st = build_case(name, torch, ae)
     if args.no_overlap:
         st["m"].model_set_overlap(False)
+    if args.no_recompute:
+        st["m"].model_set_recompute(False)
     # timed region: exactly `steps` steps, no instrumentation.  A configuration with several SNR points (cfg2, cfg4)
     # runs them as separate blocks of `steps` steps each: every point is reported, `value` is the rate over all of them.
     per_snr, dt = [], 0.0
@@ -842,6 +847,7 @@ def main():
         "config": {"workload": "%s: %s" % (name, cfg["spec"]), "batch": st["B"], "snr_db": cfg["snr_db"],
                    "seed": cfg["seed"], "pass": "forward+loss+backward" if cfg["backward"] else "forward",
                    "backward_streams": 1 if args.no_overlap else 2,
+                   "first_layer_conv_output": "stored" if args.no_recompute else "recomputed where the layer allows",
                    "inference_mode_and_static_params": not cfg["backward"]},
         "per_snr": per_snr,
         "roofline": roofline_of(rows, cfg["dtype"], name, ae),

@@ -205,6 +205,15 @@ int model_set_inference(ae_model* m, int on);
  * pass after this call, and again whenever a different params pointer is passed.  Call it again (on = 1) after
  * changing the values in place, or with on = 0 to return to converting in every pass (the default). */
 int model_set_params_static(ae_model* m, int on);
+/* Recomputation instead of storage (an execution detail, not part of the method).  When the first layer is a 3x3
+ * convolution of at most 4 input channels into 32 or 64 channels followed by batch-norm, ReLU and 2x2 max-pooling
+ * (bfloat16, image a whole number of 256-pixel patches), its convolution output — the largest tensor of the
+ * network — is by default (on = 1) never written: the statistics pass, the normalise-activate-pool pass and the
+ * two passes of its backward step each recompute it from the input (K = 27), and model_get_conv_output rebuilds it
+ * from the x and params of the last model_forward, which must still be valid then.  on = 0 stores it as for any
+ * other layer.  Every stored value is computed by the same arithmetic either way (sums run in another order).
+ * A backward pass needs a forward pass after the last change of this setting. */
+int model_set_recompute(ae_model* m, int on);
 int model_timing_slots(const ae_model* m, int* n_slots);
 int model_timing_read(ae_model* m, int slot, char* name, int name_len, double* total_ms, int64_t* launches,
                       double* flops_per_launch, double* bytes_per_launch);

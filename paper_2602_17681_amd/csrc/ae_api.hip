@@ -67,6 +67,9 @@ struct ae_model {
   bool params_static = false;       // the caller promises unchanged parameters: repack only once per direction
   const void* fwd_packed = nullptr; // parameter blob whose forward / input-gradient packing is still valid
   const void* bwd_packed = nullptr;
+  bool recompute = true;            // first-layer conv output recomputed instead of stored where the plan allows (model_set_recompute)
+  const void* last_x = nullptr;     // input and parameters of the last forward pass: a first layer whose conv output is
+  const void* last_params = nullptr; // recomputed rather than stored rebuilds it from these for model_get_conv_output
 };
 
 using namespace ae;
@@ -281,6 +284,27 @@ int forward_conv(ae_model* m, int si, Step& st, const float* params, const void*
   int nblk = 0;
   const double conv_flops = 2.0 * raw_el * st.cin * st.k * st.k;
   const double conv_bytes = (in_el + raw_el + wel) * es;
+  if (st.recompute && m->recompute) {
+    // statistics pass, finalize, then convolution + batch-norm + ReLU + pool in one kernel: the conv output stays on chip
+    const float* gb = params + st.bn_off;
+    const float* wsrc = params + st.w_off;
+    if (P.bn_mode == 0) {
+      TIMED(si, "fwd.thin_first_stats", conv_flops, in_el * es,
+            launch_thin_first(0, in, wsrc, st.wpack, a.bias, nullptr, nullptr, nullptr, m->partial, nullptr, P.batch, st.hc,
+                              st.wc, st.cin, st.cout, s));
+      wsrc = nullptr;   // packed by the statistics pass
+      TIMED(si, "fwd.bn_finalize", 0.0, (double)thin_first_blocks(P.batch, st.hc, st.wc, 0) * 2 * st.cout * 4,
+            launch_bn_finalize(m->partial, thin_first_blocks(P.batch, st.hc, st.wc, 0), rows, st.cout, gb, nullptr, a.bias,
+                               st.bn_vec, s));
+    } else {
+      TIMED(si, "fwd.bn_finalize", 0.0, 0.0,
+            launch_bn_finalize(nullptr, 0, rows, st.cout, gb, gb + 2 * st.cout, nullptr, st.bn_vec, s));
+    }
+    TIMED(si, "fwd.thin_first_bn_act_pool", conv_flops, (in_el + out_el) * es,
+          launch_thin_first(1, in, wsrc, st.wpack, a.bias, st.bn_vec, nullptr, st.out, nullptr, nullptr, P.batch, st.hc,
+                            st.wc, st.cin, st.cout, s));
+    return AE_OK;
+  }
   if (st.thin == 1 && thin_in_mfma_supported(st.cin, st.cout, st.k, st.up, P.dtype) && !a.y_aux) {
     if (st.has_bn && P.bn_mode == 0) {
       a.partial = m->partial;
@@ -341,6 +365,35 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
   const double in_el = (double)P.batch * st.cin * st.hin * st.win, raw_el = (double)rows * st.cout;
   const double out_el = (double)P.batch * st.cout * st.hout * st.wout;
   const double conv_flops = 2.0 * raw_el * st.cin * st.k * st.k;
+  if (st.recompute && m->recompute) {
+    // sums of the batch-norm backward and the weight gradient, each from the recomputed conv output; the
+    // conv-output gradient exists only as LDS slabs inside the second kernel
+    const int nb = thin_first_blocks(P.batch, st.hc, st.wc, 2);
+    TIMED(si, "bwd.thin_first_sums", conv_flops, (in_el + out_el) * es,
+          launch_thin_first(2, in, nullptr, st.wpack, params + st.b_off, st.bn_vec, g, nullptr, m->partial, nullptr, P.batch,
+                            st.hc, st.wc, st.cin, st.cout, s));
+    TIMED(si, "bwd.bn_finalize", 0.0, 0.0,
+          launch_bn_bwd_finalize(m->partial, nb, rows, st.cout, grads + st.b_off, st.bn_vec, grads + st.bn_off,
+                                 P.bn_mode == 0, s));
+    hipStream_t ws = s;
+    hipStream_t side = side_stream(m);
+    if (side) {
+      AE_HIP(hipEventRecord(m->ev_fork, s));
+      AE_HIP(hipStreamWaitEvent(side, m->ev_fork, 0));
+      ws = side;
+    } else {
+      AE_TRY(join_side(m, 0, s));
+      AE_TRY(join_side(m, 1, s));
+    }
+    TIMED_ON(ws, si, "bwd.thin_first_wgrad", 2.0 * conv_flops, (in_el + out_el) * es + wel * 4,
+             launch_thin_first(3, in, nullptr, st.wpack, params + st.b_off, st.bn_vec, g, nullptr, m->wgrad_ws,
+                               grads + st.w_off, P.batch, st.hc, st.wc, st.cin, st.cout, ws));
+    if (ws != s) {
+      AE_HIP(hipEventRecord(m->ev_wdone[m->draw_sel], ws));
+      m->wpending[m->draw_sel] = true;
+    }
+    return AE_OK;   // the first layer needs no input gradient
+  }
   const void* dr = g;  // gradient w.r.t. the conv output (bias included)
   bool bias_done = st.has_bn;   // a batch-norm step gets its bias gradient from bn_bwd_finalize
   if (st.has_bn || st.pool || st.act != ACT_NONE) {
@@ -547,6 +600,8 @@ int model_create(const char* layer_spec, int batch, int dtype, int bn_mode, ae_m
       a.n = P.batch; a.hc = st.hc; a.wc = st.wc; a.cin = st.cin; a.cout = st.cout; a.k = st.k; a.up = st.up;
       a.dtype = P.dtype;
       st.mfma = conv_mfma_supported(a);
+      st.recompute = st.thin == 1 && !st.needs_dx && st.has_bn && st.act == ACT_RELU && st.pool &&
+                     thin_first_supported(st.cin, st.cout, st.k, st.up, P.dtype, st.hc, st.wc);
       if (st.mfma && st.thin == 0 && st.up && st.k == 3) {
         // the cheaper forms of an upsampled conv, decided once (the weight packing depends on it)
         ConvArgs f = a;
@@ -609,6 +664,13 @@ int model_set_inference(ae_model* m, int on) {
   if (!m) return fail(AE_EINVAL, "model_set_inference: null model");
   m->inference = on != 0;
   m->have_forward = false;
+  return AE_OK;
+}
+
+int model_set_recompute(ae_model* m, int on) {
+  if (!m) return fail(AE_EINVAL, "model_set_recompute: null model");
+  m->recompute = on != 0;
+  m->have_forward = false;      // a backward pass needs a forward pass taken the same way
   return AE_OK;
 }
 
@@ -697,6 +759,8 @@ int model_forward(ae_model* m, const void* params, const void* x, float snr_db, 
                              m->partial, sigma, seed, m->first_sample, s));
     return AE_OK;
   }
+  m->last_x = x;
+  m->last_params = params;
   AE_TRY(join_pack(m, s, true));
   if (m->params_static && m->fwd_packed == params) {
     m->packed_in_batch = true;     // the packed copies of an earlier call are still valid
@@ -900,6 +964,12 @@ int model_get_conv_output(ae_model* m, int step, int64_t chw[3], float* out_nchw
   if (chw) { chw[0] = st.cout; chw[1] = st.hc; chw[2] = st.wc; }
   if (!out_nchw) return AE_OK;
   if (!m->have_forward) return fail(AE_ESTATE, "model_get_conv_output: no forward pass yet");
+  if (st.recompute && m->recompute) {
+    // not kept by the forward pass: computed again, into the buffer the plan reserves for it
+    const float* prm = (const float*)m->last_params;
+    AE_TRY(launch_thin_in_mfma(m->last_x, prm + st.w_off, st.wpack, prm + st.b_off, st.raw, nullptr, P.batch, st.hc, st.wc,
+                               st.cin, st.cout, 0, ACT_NONE, 0, (hipStream_t)stream));
+  }
   return launch_to_f32_nchw(st.raw, out_nchw, P.batch, st.cout, st.hc * st.wc, P.dtype, (hipStream_t)stream);
 }
 

@@ -453,6 +453,342 @@ __global__ void k_thin_wgrad_mfma_reduce(const float* __restrict__ partial, int 
 }
 
 // ---------------------------------------------------------------------------
+// The vector path of thin_fill_patch in two halves, so that the global loads of the next patch are
+// in flight while the current one is computed.  rows * IW/8 <= NT and 2 * rows <= NT (one interior
+// chunk and one halo cell per thread at most): true for every patch of 256 pixels at least 16 wide.
+// ---------------------------------------------------------------------------
+struct ThinPatchRegs { uint4 c[4]; uint32_t e[4]; };
+
+__device__ __forceinline__ void thin_patch_load(ThinPatchRegs& R, const bf16_t* __restrict__ img, int H, int W, int CT,
+                                                int h_first, int w_first, int rows, int IW) {
+  const int tid = threadIdx.x;
+  const int64_t HW = (int64_t)H * W;
+  const int cpr = IW >> 3;
+  if (tid < rows * cpr) {
+    const int pr = tid / cpr, c = tid - pr * cpr;
+    const int hh = h_first + pr, ww = w_first + 8 * c;
+    const int64_t off = (int64_t)min(max(hh, 0), H - 1) * W + min(ww, W - 8);
+#pragma unroll
+    for (int ci = 0; ci < 4; ++ci) R.c[ci] = *reinterpret_cast<const uint4*>(img + (int64_t)min(ci, CT - 1) * HW + off);
+  }
+  const int hidx = NT - 1 - tid;
+  if (hidx < rows * 2) {
+    const int pr = hidx >> 1, side = hidx & 1;
+    const int hh = h_first + pr, ww = side ? w_first + IW : w_first - 1;
+    const int64_t off = (int64_t)min(max(hh, 0), H - 1) * W + min(max(ww, 0), W - 1);
+#pragma unroll
+    for (int ci = 0; ci < 4; ++ci) R.e[ci] = (uint32_t)img[(int64_t)min(ci, CT - 1) * HW + off];
+  }
+}
+
+__device__ __forceinline__ void thin_patch_store(const ThinPatchRegs& R, bf16_t* __restrict__ tile, int H, int W, int CT,
+                                                 int h_first, int w_first, int rows, int IW) {
+  const int PW = IW + 4;
+  const int tid = threadIdx.x;
+  const int cpr = IW >> 3;
+  if (tid < rows * cpr) {
+    const int pr = tid / cpr, c = tid - pr * cpr;
+    const int hh = h_first + pr, ww = w_first + 8 * c;
+    const bool ok = hh >= 0 && hh < H && ww < W;
+    uint32_t v[4][4];
+#pragma unroll
+    for (int ci = 0; ci < 4; ++ci) {
+      const bool keep = ok && ci < CT;
+      v[ci][0] = keep ? R.c[ci].x : 0u; v[ci][1] = keep ? R.c[ci].y : 0u;
+      v[ci][2] = keep ? R.c[ci].z : 0u; v[ci][3] = keep ? R.c[ci].w : 0u;
+    }
+    bf16_t* dst = tile + ((int64_t)pr * PW + 2 + 8 * c) * 4;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {                // word k holds pixels 2k (low half) and 2k+1 (high half)
+      uint4 o;
+      o.x = (v[0][k] & 0xFFFFu) | (v[1][k] << 16);
+      o.y = (v[2][k] & 0xFFFFu) | (v[3][k] << 16);
+      o.z = (v[0][k] >> 16) | (v[1][k] & 0xFFFF0000u);
+      o.w = (v[2][k] >> 16) | (v[3][k] & 0xFFFF0000u);
+      *reinterpret_cast<uint4*>(dst + 8 * k) = o;
+    }
+  }
+  const int hidx = NT - 1 - tid;
+  if (hidx < rows * 2) {
+    const int pr = hidx >> 1, side = hidx & 1;
+    const int hh = h_first + pr, ww = side ? w_first + IW : w_first - 1;
+    const bool ok = hh >= 0 && hh < H && ww >= 0 && ww < W;
+    uint32_t e[4];
+#pragma unroll
+    for (int ci = 0; ci < 4; ++ci) e[ci] = (ok && ci < CT) ? R.e[ci] : 0u;
+    const uint32_t lo = e[0] | (e[1] << 16), hi = e[2] | (e[3] << 16);
+    if (side) *reinterpret_cast<uint4*>(tile + ((int64_t)pr * PW + IW + 2) * 4) = make_uint4(lo, hi, 0u, 0u);
+    else *reinterpret_cast<uint4*>(tile + (int64_t)pr * PW * 4) = make_uint4(0u, 0u, lo, hi);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// First layer followed by batch-norm, ReLU and 2x2 max-pool, with its convolution output never in
+// memory.  K = 27 makes the convolution nearly free on the matrix cores, while its output is the
+// largest tensor of the network (C_out/C_in times the input): every pass that needs the output
+// recomputes it from the input patch instead of reading it.  Row quads of the accumulator tiles are
+// 2x2 pooling windows (thin_row_pixel<true>), so a lane holds the four candidates x_0..x_3 of a window.
+//   PASS 0  column statistics of the rounded convolution output -> partial[block][sum | sum sq][CW]
+//   PASS 1  pooled activation  out[n][H/2][W/2][CW] = max_k relu(scale*x_k + shift)
+//   PASS 2  sums of the batch-norm backward: partial[block][sum dy | sum dy*xhat][CW], dy being the
+//           pooled gradient at the window's winner where its pre-activation is positive
+//   PASS 3  dx_k = scale*(dy_k - c1 - xhat_k*c2), rounded to storage, kept in LDS as the pixel-major slab
+//           the weight-gradient MFMAs of k_thin_wgrad_mfma read: partial[block][CW][64]
+// Rounding to storage and x -> scale*x + shift are monotonic, so the window's maximum activation is
+// relu(scale*x_w + shift) with x_w the rounded maximum of the window for scale > 0, the minimum for
+// scale < 0, x_0 for scale = 0 (all equal: the first wins) — passes 1 and 2 need nothing else of the
+// window, and give the bits of k_post_forward / PostBwdWindow.  Pass 3 finds the winner as the first
+// k whose pre-activation equals the maximum, and evaluates dx_k as alpha*x_k + beta (+ scale*dy at the
+// winner) with alpha = -scale*c2*invstd, beta = scale*(c2*invstd*mean - c1): the formula of
+// k_post_bwd_apply up to binary32 rounding, before the rounding to storage.
+// Patches are interior (H, W multiples of the patch), CW = 32*NJ, the input 16-byte aligned with
+// W % 8 == 0; a workgroup walks over patches t = blockIdx.x, blockIdx.x + gridDim.x, ... and has the
+// next patch's global loads in flight while it computes.
+// ---------------------------------------------------------------------------
+template <int NJ, int PASS>
+__global__ __launch_bounds__(NT, PASS == 3 ? 2 : 1) void k_thin_first(
+    const bf16_t* __restrict__ thin, const bf16_t* __restrict__ wfrag, const float* __restrict__ bias,
+    const float* __restrict__ bn_vec, const bf16_t* __restrict__ dout, bf16_t* __restrict__ out,
+    float* __restrict__ partial, int H, int W, int CT, int TW, int tw_shift, int tiles_w, int tiles_h, int ntiles) {
+  constexpr int CW = NJ * 32;
+  constexpr int MAXT = 408;                     // (TH+2)*(TW+4) cells for every TW in {16,32,64}
+  constexpr int SW = CW + 8;                    // row stride of the staged pooled outputs
+  constexpr int LA = CW + 16;                   // row stride of the gradient slab
+  constexpr int CPR = CW / 8;                   // 16-byte chunks per pixel
+  constexpr int GCH = 64 * CPR;                 // chunks of the pooled-gradient tile (64 windows)
+  constexpr int GPT = (GCH + NT - 1) / NT;
+  __shared__ __attribute__((aligned(16))) bf16_t tile[MAXT * 4];
+  __shared__ __attribute__((aligned(16))) bf16_t sG[PASS >= 2 ? 64 * CW : 8];
+  __shared__ __attribute__((aligned(16))) bf16_t sW[PASS == 3 ? NT * LA : (PASS == 1 ? 4 * 8 * SW : 8)];
+  __shared__ float sRed[(PASS == 0 || PASS == 2) ? 4 * 2 * CW : 1];
+  const int TH = NT >> tw_shift;
+  const int PW = TW + 4;
+  const int Hq = H >> 1, Wq = W >> 1;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int frag_row = lane & 31, g = lane >> 5, col_lane = lane & 31;
+
+  t_bf16x8 bfrag[3][NJ];
+#pragma unroll
+  for (int r = 0; r < 3; ++r)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+      bfrag[r][j] = *reinterpret_cast<const t_bf16x8*>(&wfrag[((j * 32 + frag_row) * 3 + r) * 16 + g * 8]);
+  float bs[NJ], sc[NJ], sh[NJ], mu[NJ], is[NJ], al[NJ], be[NJ], s1[NJ], s2[NJ];
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int c = j * 32 + col_lane;
+    bs[j] = bias ? bias[c] : 0.0f;
+    sc[j] = PASS >= 1 ? bn_vec[c] : 1.0f;
+    sh[j] = PASS >= 1 ? bn_vec[CW + c] : 0.0f;
+    mu[j] = PASS >= 2 ? bn_vec[2 * CW + c] : 0.0f;
+    is[j] = PASS >= 2 ? bn_vec[3 * CW + c] : 1.0f;
+    const float c1 = PASS == 3 ? bn_vec[4 * CW + c] : 0.0f;
+    const float c2 = PASS == 3 ? bn_vec[5 * CW + c] : 0.0f;
+    al[j] = -(sc[j] * c2) * is[j];
+    be[j] = sc[j] * (c2 * is[j] * mu[j] - c1);
+    s1[j] = 0.0f; s2[j] = 0.0f;
+  }
+  t_floatx16 wacc[PASS == 3 ? NJ : 1][2];
+  if (PASS == 3) {
+#pragma unroll
+    for (int i = 0; i < NJ; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) wacc[i][j][e] = 0.0f;
+  }
+
+  // patch t: image n, rows h0 .., columns w0 ..
+  auto where = [&](int t, int& n, int& h0, int& w0) {
+    const int tx = t % tiles_w; t /= tiles_w;
+    const int ty = t % tiles_h;
+    n = t / tiles_h; h0 = ty * TH; w0 = tx * TW;
+  };
+  ThinPatchRegs pre;
+  static_assert(GPT <= 2, "pooled-gradient tile: at most two chunks per thread");
+  uint4 gv0 = make_uint4(0u, 0u, 0u, 0u), gv1 = gv0;
+  auto prefetch = [&](int t) {
+    int n, h0, w0;
+    where(t, n, h0, w0);
+    thin_patch_load(pre, thin + (int64_t)n * CT * H * W, H, W, CT, h0 - 1, w0, TH + 2, TW);
+    if (PASS >= 2) {
+      auto chunk = [&](int idx) {
+        const int G = idx / CPR, ch = idx % CPR;
+        const int hq = (h0 >> 1) + (G >> (tw_shift - 1)), wq = (w0 >> 1) + (G & ((TW >> 1) - 1));
+        return *reinterpret_cast<const uint4*>(dout + (((int64_t)n * Hq + hq) * Wq + wq) * CW + ch * 8);
+      };
+      gv0 = chunk(min(tid, GCH - 1));
+      if (GPT == 2) gv1 = chunk(min(NT + tid, GCH - 1));
+    }
+  };
+  prefetch(blockIdx.x);
+
+  for (int t = blockIdx.x; t < ntiles; t += gridDim.x) {
+    int n, h0, w0;
+    where(t, n, h0, w0);
+    __syncthreads();                            // the previous patch is fully consumed
+    thin_patch_store(pre, tile, H, W, CT, h0 - 1, w0, TH + 2, TW);
+    if (PASS >= 2) {
+      if (tid < GCH) *reinterpret_cast<uint4*>(&sG[tid * 8]) = gv0;
+      if (GPT == 2 && NT + tid < GCH) *reinterpret_cast<uint4*>(&sG[(NT + tid) * 8]) = gv1;
+    }
+    __syncthreads();
+    if (t + (int)gridDim.x < ntiles) prefetch(t + gridDim.x);
+
+    t_floatx16 acc[2][NJ];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < NJ; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      int th, tw;
+      thin_row_pixel<true>(wave * 64 + i * 32 + frag_row, TW, tw_shift, th, tw);
+#pragma unroll
+      for (int r = 0; r < 3; ++r) {
+        const bf16_t* src = &tile[((th + r) * PW + tw + 1 + 2 * g) * 4];
+        union { uint2 u[2]; t_bf16x8 v; } a;
+        a.u[0] = *reinterpret_cast<const uint2*>(src);
+        a.u[1] = *reinterpret_cast<const uint2*>(src + 4);
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, bfrag[r][j], acc[i][j], 0, 0, 0);
+      }
+    }
+
+    bf16_t* stage = sW + wave * (8 * SW);        // PASS 1 only
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) {
+#pragma unroll
+        for (int eg = 0; eg < 4; ++eg) {
+          float x[4];                            // the window's conv outputs before rounding
+#pragma unroll
+          for (int k = 0; k < 4; ++k) x[k] = acc[i][j][4 * eg + k] + bs[j];
+          if (PASS == 0) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+              const float d = bf16_to_f32(f32_to_bf16(x[k])) - bs[j];   // statistics about the channel's bias (see k_bn_finalize)
+              s1[j] += d;
+              s2[j] = fmaf(d, d, s2[j]);
+            }
+          } else if (PASS <= 2) {
+            const float hi = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
+            const float lo = fminf(fminf(x[0], x[1]), fminf(x[2], x[3]));
+            const float xw = bf16_to_f32(f32_to_bf16(sc[j] > 0.0f ? hi : (sc[j] < 0.0f ? lo : x[0])));
+            const float pre_w = fmaf(sc[j], xw, sh[j]);
+            if (PASS == 1) {
+              stage[(eg * 2 + g) * SW + j * 32 + col_lane] = f32_to_bf16(apply_act(pre_w, ACT_RELU));
+            } else {
+              const int G = wave * 16 + i * 8 + eg * 2 + g;
+              const float gg = bf16_to_f32(sG[G * CW + j * 32 + col_lane]);
+              const float dyw = pre_w > 0.0f ? gg : 0.0f;
+              s1[j] += dyw;
+              s2[j] = fmaf(dyw, (xw - mu[j]) * is[j], s2[j]);
+            }
+          } else {
+            const int G = wave * 16 + i * 8 + eg * 2 + g;
+            const float gg = bf16_to_f32(sG[G * CW + j * 32 + col_lane]);
+            float pk[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+              x[k] = bf16_to_f32(f32_to_bf16(x[k]));
+              pk[k] = fmaf(sc[j], x[k], sh[j]);
+            }
+            const float pm = fmaxf(fmaxf(pk[0], pk[1]), fmaxf(pk[2], pk[3]));
+            const float sdy = pm > 0.0f ? sc[j] * gg : 0.0f;         // scale*dy at the winner
+            const int arg = pk[0] == pm ? 0 : (pk[1] == pm ? 1 : (pk[2] == pm ? 2 : 3));
+            int th, tw;
+            thin_row_pixel<true>(wave * 64 + i * 32 + eg * 8 + g * 4, TW, tw_shift, th, tw);
+            bf16_t* dst = &sW[(th * TW + tw) * LA + j * 32 + col_lane];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+              const float o = fmaf(al[j], x[k], be[j]) + (arg == k ? sdy : 0.0f);
+              dst[((k >> 1) * TW + (k & 1)) * LA] = f32_to_bf16(o);
+            }
+          }
+        }
+      }
+      if (PASS == 1) {
+        bf16_t* out_n = out + (int64_t)n * Hq * Wq * CW;
+#pragma unroll
+        for (int c = 0; c < (8 * CPR + 63) / 64; ++c) {
+          const int idx = c * 64 + lane;
+          const int g8 = idx / CPR, ch = idx % CPR;
+          const int G = wave * 16 + i * 8 + g8;
+          const int hq = (h0 >> 1) + (G >> (tw_shift - 1)), wq = (w0 >> 1) + (G & ((TW >> 1) - 1));
+          if (idx < 8 * CPR)
+            *reinterpret_cast<uint4*>(out_n + ((int64_t)hq * Wq + wq) * CW + ch * 8) =
+                *reinterpret_cast<const uint4*>(&stage[g8 * SW + ch * 8]);
+        }
+      }
+    }
+
+    if (PASS == 3) {
+      __syncthreads();                          // the slab is complete
+      const int grp = lane >> 4, sl = lane & 15;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        const int p0 = wave * 64 + ks * 16;     // 16 consecutive pixels of one patch row
+        const int th = p0 >> tw_shift, tw0 = p0 & (TW - 1);
+        const int psub = 8 * (grp >> 1) + (sl >> 2);
+        t_bf16x8 a[NJ], bfr[2];
+#pragma unroll
+        for (int i = 0; i < NJ; ++i) {
+          const bf16_t* q = &sW[(p0 + psub) * LA + i * 32 + 16 * (grp & 1) + 4 * (sl & 3)];
+          a[i] = thin_tr_frag(q, q + 4 * LA);
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const int r = min(2 * j + (grp & 1), 2);  // columns 48..63 are unused: any finite data
+          const bf16_t* q = &tile[((th + r) * PW + 1 + tw0 + psub + (sl & 3)) * 4];
+          bfr[j] = thin_tr_frag(q, q + 16);
+        }
+#pragma unroll
+        for (int i = 0; i < NJ; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j) wacc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bfr[j], wacc[i][j], 0, 0, 0);
+      }
+    }
+  }
+
+  if (PASS == 0 || PASS == 2) {
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      const float t1 = s1[j] + __shfl_xor(s1[j], 32, 64);
+      const float t2 = s2[j] + __shfl_xor(s2[j], 32, 64);
+      if (lane < 32) { sRed[(wave * 2 + 0) * CW + j * 32 + col_lane] = t1; sRed[(wave * 2 + 1) * CW + j * 32 + col_lane] = t2; }
+    }
+    __syncthreads();
+    for (int i = tid; i < 2 * CW; i += NT)
+      partial[(int64_t)blockIdx.x * 2 * CW + i] = (sRed[i] + sRed[2 * CW + i]) + (sRed[4 * CW + i] + sRed[6 * CW + i]);
+  }
+  if (PASS == 3) {
+    // sum the four waves in a fixed order through LDS (reusing the slab), then write [cw][64]
+    float* sF = reinterpret_cast<float*>(sW);   // NJ*2*1024 floats <= NT*LA*2 bytes
+    for (int wv = 0; wv < 4; ++wv) {
+      __syncthreads();
+      if (wave == wv) {
+#pragma unroll
+        for (int i = 0; i < NJ; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+              const int row = i * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3), col = j * 32 + (lane & 31);
+              if (wv == 0) sF[row * 64 + col] = wacc[i][j][e];
+              else sF[row * 64 + col] += wacc[i][j][e];
+            }
+      }
+    }
+    __syncthreads();
+    for (int i = tid; i < CW * 64; i += NT) partial[(int64_t)blockIdx.x * CW * 64 + i] = sF[i];
+  }
+}
+
+// ---------------------------------------------------------------------------
 // thin-out conv (forward of the last layer, optionally through the x2 upsample):
 //   out[n][ct][y][x] = act( b[ct] + sum_{r,s,cw} wide[n][(y+r-1)>>up][(x+s-1)>>up][cw] * W[ct][cw][r][s] )
 // as a small GEMM followed by a shifted sum.  For every wide pixel q of a patch (TH x TW pixels
@@ -624,6 +960,62 @@ int launch_thin_in_mfma(const void* thin, const float* wcanon, void* wfrag, cons
 #undef LAUNCH_TIM_NJ
 #undef LAUNCH_TIM
   return launch_status("thin_in_mfma");
+}
+
+// First layer + batch-norm + ReLU + 2x2 max-pool with the convolution output recomputed in every
+// pass (k_thin_first).  Whole patches only, 32 or 64 output channels.
+bool thin_first_supported(int ct, int cw, int k, int up, int dtype, int h, int w) {
+  if (!thin_in_mfma_supported(ct, cw, k, up, dtype) || cw > 64 || w % 8 != 0) return false;
+  const ThinTile t = thin_tile(1, h, w);
+  return t.tw >= 16 && h % t.th == 0 && w % t.tw == 0;
+}
+
+// workgroups of a pass (each walks the same number of patches when the patch count is a multiple)
+static int thin_first_grid(int tiles, int pass) {
+  const int cap = pass >= 2 ? 512 : 768;        // resident workgroups: registers allow two (passes 2, 3) or three per compute unit
+  return tiles < cap ? tiles : cap;
+}
+int thin_first_blocks(int n, int h, int w, int pass) { return thin_first_grid(thin_tile(n, h, w).blocks, pass); }
+
+// pass 0: partial <- column statistics (packs wfrag from wcanon first);  pass 1: out <- pooled activation;
+// pass 2: partial <- batch-norm backward sums from the pooled gradient dout;
+// pass 3: workspace, dw_canonical <- weight gradient.  Passes 1-3 read the wfrag an earlier pass 0 / pack left.
+int launch_thin_first(int pass, const void* thin, const float* wcanon, void* wfrag, const float* bias,
+                      const float* bn_vec, const void* dout, void* out, float* partial, float* dw_canonical, int n, int h,
+                      int w, int ct, int cw, hipStream_t s) {
+  if (pass < 0 || pass > 3 || !thin_first_supported(ct, cw, 3, 0, AE_BF16, h, w))
+    return fail(AE_EINVAL, "thin_first: shape not supported");
+  if (((uintptr_t)thin & 15) != 0) return fail(AE_EINVAL, "thin_first: input must be 16-byte aligned");
+  const ThinTile t = thin_tile(n, h, w);
+  const int nj = cw / 32;
+  if (wcanon) {
+    hipLaunchKernelGGL(k_thin_pack_wfrag, dim3((unsigned)((nj * 32 * 48 + NT - 1) / NT)), dim3(NT), 0, s, wcanon,
+                       (bf16_t*)wfrag, ct, cw, nj * 32, 0);
+    AE_TRY(launch_status("thin_pack_wfrag"));
+  }
+  const int grid = thin_first_grid(t.blocks, pass);
+#define LAUNCH_TF(NJV, PASSV)                                                                                      \
+  hipLaunchKernelGGL((k_thin_first<NJV, PASSV>), dim3((unsigned)grid), dim3(NT), 0, s, (const bf16_t*)thin,          \
+                     (const bf16_t*)wfrag, bias, bn_vec, (const bf16_t*)dout, (bf16_t*)out, partial, h, w, ct, t.tw, \
+                     t.shift, t.tiles_w, t.tiles_h, t.blocks)
+#define LAUNCH_TF_NJ(PASSV) \
+  if (nj == 1) LAUNCH_TF(1, PASSV); else LAUNCH_TF(2, PASSV)
+  switch (pass) {
+    case 0: LAUNCH_TF_NJ(0); break;
+    case 1: LAUNCH_TF_NJ(1); break;
+    case 2: LAUNCH_TF_NJ(2); break;
+    default: LAUNCH_TF_NJ(3); break;
+  }
+#undef LAUNCH_TF_NJ
+#undef LAUNCH_TF
+  AE_TRY(launch_status("thin_first"));
+  if (pass == 3) {
+    const int total = cw * ct * 9;
+    hipLaunchKernelGGL(k_thin_wgrad_mfma_reduce, dim3((unsigned)((total * 16 + NT - 1) / NT)), dim3(NT), 0, s, partial,
+                       grid, cw, ct, 0, dw_canonical);
+    return launch_status("thin_wgrad_mfma_reduce");
+  }
+  return AE_OK;
 }
 
 bool thin_out_mfma_supported(int ct, int cw, int k, int dtype) {

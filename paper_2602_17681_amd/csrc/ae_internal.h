@@ -70,6 +70,7 @@ struct Step {
   bool up_phases = false;           // forward of an upsampled conv as four 2x2 phase convolutions (CONV_UP_PHASES)
   bool up_dgrad = false;            // its input gradient as one 4x4 stride-2 convolution (CONV_UP_DGRAD)
   int thin = 0;                     // 1: thin-in kernels (input is the planar boundary tensor); 2: thin-out kernels
+  bool recompute = false;           // thin-in + bn + relu + pool2: the conv output is recomputed by every pass that needs it, never stored
   bool out_planar = false;          // `out` is stored planar [n][C][H][W] (thin-out step)
 };
 
@@ -216,6 +217,12 @@ int thin_in_mfma_blocks(int n, int h, int w);   // = number of partial-sum block
 int64_t thin_wfrag_bytes(int cw);               // scratch for the repacked weights
 int launch_thin_in_mfma(const void* thin, const float* wcanon, void* wfrag, const float* bias, void* out, float* partial,
                         int n, int h, int w, int ct, int cw, int flip, int act, int upsum, hipStream_t s);
+// first layer + batch-norm + ReLU + pool2 with the convolution output recomputed in every pass
+bool thin_first_supported(int ct, int cw, int k, int up, int dtype, int h, int w);
+int thin_first_blocks(int n, int h, int w, int pass);   // = partial blocks pass 0 / 2 write
+int launch_thin_first(int pass, const void* thin, const float* wcanon, void* wfrag, const float* bias,
+                      const float* bn_vec, const void* dout, void* out, float* partial, float* dw_canonical, int n, int h,
+                      int w, int ct, int cw, hipStream_t s);
 bool thin_out_mfma_supported(int ct, int cw, int k, int dtype);
 int64_t thin_out_wz_bytes(int ct, int cw);
 int launch_thin_out_mfma(const void* wide, const float* wcanon, void* wz, const float* bias, void* out, float* out_f32,

@@ -236,6 +236,66 @@ def test_inference_mode_small_image_path(ae, case):
     m.close()
 
 
+FIRST_LAYER_RECOMPUTED = [
+    # (spec, batch): first layer conv3 of <= 4 channels into 32 / 64 channels + bn + relu + pool2 in bf16, image a
+    # whole number of 256-pixel patches (patch widths 16, 32, 64; two patch columns; one or two MFMA column tiles)
+    ("in:3x16x16,conv3:32,bn,relu,pool2,conv3:32,relu,up2,conv3:3,sigmoid", 5),
+    ("in:1x32x32,conv3:64,bn,relu,pool2,conv3:32,bn,relu,pool2,conv1:8,pnorm,awgn,conv1:32,up2,conv3:32,relu,up2,conv3:1,sigmoid", 3),
+    ("in:4x8x128,conv3:64,bn,relu,pool2,conv3:32,relu,up2,conv3:4,sigmoid", 2),
+    ("in:2x64x64,conv3:32,bn,relu,pool2,conv3:32,relu,up2,conv3:2,sigmoid", 9),
+]
+
+
+@pytest.mark.parametrize("case", range(len(FIRST_LAYER_RECOMPUTED)))
+@pytest.mark.parametrize("bn_mode", [0, 1])
+def test_first_layer_conv_output_recomputed_not_stored(ae, case, bn_mode):
+    """A first layer conv3 + bn + relu + pool2 in bf16 never writes its convolution output: statistics, pooled
+    activation, batch-norm backward sums and weight gradient each recompute it from the input.  Parity of the whole
+    network against the oracle at the usual bars (the counted-decisions bar for the gradients), the timing slots
+    show the path was taken, and the stored-output path of the same library (model_set_recompute(0)) gives the same
+    pooled activation up to the rounding of statistics summed in another order, and gradients to 1e-2."""
+    import torch
+    spec, batch = FIRST_LAYER_RECOMPUTED[case]
+    run_case(spec, batch, dtype="bf16", seed=70 + case, snr_db=9.0, bn_mode=bn_mode, backward=True, perturb=True,
+             flips=True, tag="first-layer recompute %d" % case)
+    m = ae.Model(spec, batch, ae.AE_BF16, bn_mode)
+    p = torch.from_numpy(wl.make_params(spec, 70 + case, perturb=True, bf16=True, bn_mode=bn_mode)).cuda()
+    x = torch.from_numpy(wl.make_input(spec, batch, 70 + case, bf16=True)).cuda().to(torch.bfloat16)
+    y = torch.empty((batch,) + m.out_shape, dtype=torch.bfloat16, device="cuda")
+    dy, loss = torch.empty_like(y), torch.zeros(1, device="cuda")
+    res = []
+    for on in (1, 0, 1):
+        m.model_set_recompute(on)
+        m.model_timing_reset()
+        m.model_timing_enable(True)
+        m.model_forward(p, x, 9.0, 70 + case, y)
+        ae.model_loss_mse(y, x, loss, dy)
+        g = torch.full((m.n_params,), float("nan"), device="cuda")
+        m.model_backward(p, x, dy, g)
+        m.model_timing_enable(False)
+        names = [t["name"] for t in m.model_timing_read() if t["launches"] and t["name"].startswith("step00.")]
+        assert ("step00.fwd.thin_first_bn_act_pool" in names) == bool(on), names
+        assert ("step00.bwd.thin_first_wgrad" in names) == bool(on), names
+        assert ("step00.fwd.thin_first_stats" in names) == bool(on and bn_mode == 0), names
+        a0 = torch.empty((batch,) + m.model_step_info(0)[1], device="cuda")
+        m.model_get_activation(0, a0)
+        c0 = torch.empty((batch,) + m.model_get_conv_output(0), device="cuda")
+        m.model_get_conv_output(0, c0)
+        res.append((y.float().cpu().numpy().copy(), a0.cpu().numpy(), c0.cpu().numpy(), g.cpu().numpy()))
+    m.close()
+    for k in range(3):                                     # deterministic
+        assert np.array_equal(res[0][k], res[2][k])
+    # ... and so are the first layer's gradients (a later layer of 32 channels takes the generic fallback kernel,
+    # whose weight gradient is accumulated with floating-point atomics)
+    ent, _, _, _ = wl.param_layout(spec, bn_mode)
+    first = max(e["offset"] + int(np.prod(e["shape"])) for e in ent if e["op"] <= 1)
+    assert first > 9 * 32 and np.array_equal(res[0][3][:first], res[2][3][:first])
+    assert np.array_equal(res[0][2], res[1][2])            # the convolution output itself: same bits either way
+    assert_close(res[0][1], res[1][1], 4e-3, "pooled activation, recomputed against stored", tol_max=8e-3)
+    assert_close(res[0][0], res[1][0], 1e-2, "y, recomputed against stored", tol_max=3e-2)
+    assert_close(res[0][3], res[1][3], 1e-2, "gradients, recomputed against stored", tol_max=5e-2)
+
+
 def test_inference_mode_of_a_network_without_a_fused_path(ae):
     """Inference mode changes nothing for a network that has no special path: same bits as the default mode."""
     import torch
