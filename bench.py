@@ -705,6 +705,9 @@ def main():
     ap.add_argument("--no-recompute", action="store_true",
                     help="store the first layer's convolution output instead of recomputing it in every pass that needs it "
                          "(model_set_recompute(0)): the library's behaviour for layers that have no recomputing path")
+    ap.add_argument("--no-fused-backward", action="store_true",
+                    help="run the ReLU backward / batch-norm backward sums as passes of their own instead of in the epilogue "
+                         "of the kernel that produces the gradient (model_set_fused_backward(0))")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="only run a plain device-to-device copy of MIB MiB five times (reference for the "
                          "FETCH_SIZE / WRITE_SIZE counters of rocprofv3) and exit")
@@ -815,6 +818,8 @@ def main():
         st["m"].model_set_overlap(False)
     if args.no_recompute:
         st["m"].model_set_recompute(False)
+    if args.no_fused_backward:
+        st["m"].model_set_fused_backward(False)
     # timed region: exactly `steps` steps, no instrumentation.  A configuration with several SNR points (cfg2, cfg4)
     # runs them as separate blocks of `steps` steps each: every point is reported, `value` is the rate over all of them.
     per_snr, dt = [], 0.0

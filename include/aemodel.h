@@ -214,6 +214,13 @@ int model_set_params_static(ae_model* m, int on);
  * other layer.  Every stored value is computed by the same arithmetic either way (sums run in another order).
  * A backward pass needs a forward pass after the last change of this setting. */
 int model_set_recompute(ae_model* m, int on);
+/* Fused backward epilogues (an execution detail, not part of the method).  By default (on = 1), in bfloat16 models the
+ * kernel that computes the gradient with respect to a layer's output also does, while it stores each tile, the part
+ * of that layer's backward step which only needs the layer's saved activation beside the gradient: for a conv + ReLU
+ * layer the ReLU backward and the column sums of the bias gradient, for a conv + batch-norm + ReLU (+ pool2) layer
+ * the two sums of the batch-norm backward (sum dy, sum dy * xhat).  on = 0 runs these as passes of their own.  The
+ * stored values are the same either way; the sums are taken in another order. */
+int model_set_fused_backward(ae_model* m, int on);
 int model_timing_slots(const ae_model* m, int* n_slots);
 int model_timing_read(ae_model* m, int slot, char* name, int name_len, double* total_ms, int64_t* launches,
                       double* flops_per_launch, double* bytes_per_launch);

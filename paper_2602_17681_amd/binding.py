@@ -22,7 +22,7 @@ SYMBOLS = [
     "model_describe", "model_create", "model_destroy", "model_param_count", "model_io_shape",
     "model_set_sample_offset", "model_forward", "model_backward", "model_loss_mse", "model_noise",
     "model_pnorm_awgn", "model_gen_bits", "model_count_errors", "model_monte_carlo", "model_num_steps", "model_step_info",
-    "model_get_activation", "model_get_conv_output", "model_timing_enable", "model_set_overlap", "model_set_params_static", "model_set_inference", "model_set_recompute", "model_calibrate_mfma", "model_mx_quantize", "model_mx_quantize_elem", "model_transform_mse_workspace",
+    "model_get_activation", "model_get_conv_output", "model_timing_enable", "model_set_overlap", "model_set_params_static", "model_set_inference", "model_set_recompute", "model_set_fused_backward", "model_calibrate_mfma", "model_mx_quantize", "model_mx_quantize_elem", "model_transform_mse_workspace",
     "model_transform_mse", "model_transform_mse_elem", "model_transform_mse_static", "model_inverse_shift", "model_lu_workspace", "model_lu_compose", "model_lu_backward", "model_vol_penalty", "model_lu_inverse_workspace", "model_lu_inverse", "model_lu_compose_batch", "model_lu_backward_batch", "model_lu_inverse_batch", "model_lu_timing", "model_qr_workspace", "model_qr_squarings", "model_qr_compose", "model_qr_backward", "model_qr_inverse", "model_fold_workspace", "model_fold_linear", "model_fold_embedding", "model_timing_slots",
     "model_timing_read", "model_timing_reset", "model_last_error",
 ]
@@ -63,6 +63,7 @@ def _load():
     L.model_set_overlap.argtypes = [vp, C.c_int]
     L.model_set_params_static.argtypes = [vp, C.c_int]
     L.model_set_recompute.argtypes = [vp, C.c_int]
+    L.model_set_fused_backward.argtypes = [vp, C.c_int]
     L.model_set_inference.argtypes = [vp, C.c_int]
     L.model_calibrate_mfma.argtypes = [C.c_int, C.c_int, C.c_int, vp, C.POINTER(C.c_double), C.POINTER(C.c_double), vp]
     L.model_mx_quantize.argtypes = [vp, vp, C.c_int64, C.c_int64, C.c_int, C.c_int, vp]
@@ -201,6 +202,9 @@ class Model:
 
     def model_set_recompute(self, on):
         _check(lib.model_set_recompute(self._h, 1 if on else 0))
+
+    def model_set_fused_backward(self, on):
+        _check(lib.model_set_fused_backward(self._h, 1 if on else 0))
 
     def model_timing_reset(self):
         _check(lib.model_timing_reset(self._h))

@@ -67,6 +67,10 @@ struct ae_model {
   bool params_static = false;       // the caller promises unchanged parameters: repack only once per direction
   const void* fwd_packed = nullptr; // parameter blob whose forward / input-gradient packing is still valid
   const void* bwd_packed = nullptr;
+  bool fuse_bwd = true;             // ReLU backward / batch-norm backward sums in the epilogue of the kernel that produces the gradient (model_set_fused_backward)
+  int pre_mode = 0;                 // what the input-gradient kernel of the layer above already did for the current layer:
+  int pre_blocks = 0;               //   1: ReLU-masked gradient in the draw buffer, bias column sums in `partial` (pre_blocks row blocks);
+                                    //   2: the two batch-norm backward sums in `partial`
   bool recompute = true;            // first-layer conv output recomputed instead of stored where the plan allows (model_set_recompute)
   const void* last_x = nullptr;     // input and parameters of the last forward pass: a first layer whose conv output is
   const void* last_params = nullptr; // recomputed rather than stored rebuilds it from these for model_get_conv_output
@@ -396,7 +400,9 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
   }
   const void* dr = g;  // gradient w.r.t. the conv output (bias included)
   bool bias_done = st.has_bn;   // a batch-norm step gets its bias gradient from bn_bwd_finalize
-  if (st.has_bn || st.pool || st.act != ACT_NONE) {
+  const int pre = m->pre_mode;  // what the input-gradient kernel of the layer above already did for this layer
+  m->pre_mode = 0;
+  if ((st.has_bn || st.pool || st.act != ACT_NONE) && pre != 1) {
     // this layer's conv-output gradient goes to the other buffer than the previous layer's, and
     // only after the weight gradient that read this buffer two layers ago has finished
     m->draw_sel ^= 1;
@@ -406,12 +412,19 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
   if (st.has_bn || st.pool) {
     if (st.has_bn) {
       const int64_t prow = (int64_t)P.batch * st.hout * st.wout;
-      TIMED(si, "bwd.bn_reduce", 0.0, (st.act == ACT_RELU ? 2.0 * out_el : raw_el + out_el) * es,
-            launch_post_bwd_reduce(st.raw, g, st.out, st.bn_vec, P.batch, st.hc, st.wc, st.cout, st.act, st.pool,
-                                   P.dtype, m->partial, s));
-      TIMED(si, "bwd.bn_finalize", 0.0, 0.0,
-            launch_bn_bwd_finalize(m->partial, nblocks_for(prow), rows, st.cout, grads + st.b_off, st.bn_vec,
-                                   grads + st.bn_off, P.bn_mode == 0, s));
+      if (pre == 2) {
+        // the sums came out of the epilogue that wrote g (channels of scale 0 are redone by the finalize kernel)
+        TIMED(si, "bwd.bn_finalize", 0.0, 0.0,
+              launch_bn_bwd_finalize(m->partial, m->pre_blocks, rows, st.cout, grads + st.b_off, st.bn_vec,
+                                     grads + st.bn_off, P.bn_mode == 0, s, st.raw, g, P.batch, st.hc, st.wc, st.pool));
+      } else {
+        TIMED(si, "bwd.bn_reduce", 0.0, (st.act == ACT_RELU ? 2.0 * out_el : raw_el + out_el) * es,
+              launch_post_bwd_reduce(st.raw, g, st.out, st.bn_vec, P.batch, st.hc, st.wc, st.cout, st.act, st.pool,
+                                     P.dtype, m->partial, s));
+        TIMED(si, "bwd.bn_finalize", 0.0, 0.0,
+              launch_bn_bwd_finalize(m->partial, nblocks_for(prow), rows, st.cout, grads + st.b_off, st.bn_vec,
+                                     grads + st.bn_off, P.bn_mode == 0, s));
+      }
     }
     TIMED(si, "bwd.bn_act_pool", 0.0, (2.0 * raw_el + out_el) * es,
           launch_post_bwd_apply(st.raw, g, st.has_bn ? st.bn_vec : nullptr, m->draw, P.batch, st.hc, st.wc, st.cout,
@@ -421,6 +434,12 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
     TIMED(si, "bwd.act", 0.0, 3.0 * raw_el * es,
           launch_act_bwd(st.out, st.aux, g, m->draw, rows * st.cout, st.act, P.dtype, s));
     dr = m->draw;
+  } else if (st.act != ACT_NONE && pre == 1) {
+    // the kernel that produced the gradient masked it and left the bias gradient's column sums
+    dr = m->draw;
+    bias_done = true;
+    TIMED(si, "bwd.bias_finalize", 0.0, 0.0,
+          launch_colsum_finalize(m->partial, m->pre_blocks, st.cout, grads + st.b_off, s));
   } else if (st.act != ACT_NONE) {
     // activation backward and the bias gradient's column sums in one pass
     TIMED(si, "bwd.act_colsum", 0.0, 3.0 * raw_el * es,
@@ -473,7 +492,25 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
                launch_thin_wgrad(dr, in, m->wgrad_ws, grads + st.w_off, P.batch, st.hin, st.win, st.cout, st.cin, 1, st.up,
                                  P.dtype, ws));
     AE_TRY(wgrad_enqueued());
-    if (st.needs_dx) {
+    bool with_relu = false;
+    if (st.needs_dx && m->fuse_bwd && st.up == 1 && si > 0 &&
+        thin_first_supported(st.cout, st.cin, st.k, 0, P.dtype, st.hc, st.wc)) {
+      const Step& pv = P.steps[si - 1];
+      if (pv.kind == ST_CONV && pv.thin == 0 && pv.act == ACT_RELU && !pv.has_bn && !pv.pool && !pv.out_planar) {
+        // the input gradient goes straight into the conv-output gradient buffer of the layer below (the other one
+        // than this layer's), already masked by that layer's ReLU, with the column sums of its bias gradient
+        with_relu = true;
+        m->draw_sel ^= 1;
+        m->draw = m->draw_buf[m->draw_sel];
+        AE_TRY(join_side(m, m->draw_sel, s));
+        TIMED(si, "bwd.dgrad_thin_relu_mfma", conv_flops, (raw_el + 2.0 * in_el) * es,
+              launch_thin_first(4, dr, params + st.w_off, st.wpack_d, nullptr, nullptr, pv.out, m->draw, m->partial, nullptr,
+                                P.batch, st.hc, st.wc, st.cout, st.cin, s));
+        m->pre_mode = 1;
+        m->pre_blocks = thin_first_blocks(P.batch, st.hc, st.wc, 4);
+      }
+    }
+    if (st.needs_dx && !with_relu) {
       const double full_el = (double)rows * st.cin;
       if (thin_in_mfma_supported(st.cout, st.cin, st.k, 0, P.dtype)) {
         // the 2x2 sum that undoes the upsample happens in the kernel's epilogue
@@ -542,6 +579,29 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
     a.splitk_ws = m->splitk_ws;
     a.splitk_floats = P.max_splitk_floats;
     const double full_el = (double)rows * st.cin;
+    // Work of the layer below that fits this kernel's epilogue (it reads that layer's saved activation beside the
+    // gradient tile it is about to store): the ReLU backward + bias column sums of a conv + ReLU layer, or the two
+    // sums of the batch-norm backward of a conv + bn + ReLU (+ pool) layer.
+    if (m->fuse_bwd && si > 0 && a.y == gnext && conv_mfma_supported(a)) {
+      const Step& pv = P.steps[si - 1];
+      const int mode = (pv.kind != ST_CONV || pv.thin != 0 || pv.act != ACT_RELU || pv.out_planar || (pv.recompute && m->recompute)) ? 0
+                       : (!pv.has_bn && !pv.pool) ? 1 : (pv.has_bn ? 2 : 0);
+      const int nb = mode ? conv_comp_blocks(a) : 0;
+      if (nb > 0) {
+        a.comp = pv.out; a.comp_mode = mode; a.partial = m->partial;
+        if (mode == 1) {
+          // straight into the layer's conv-output gradient buffer (the other one than this layer's)
+          m->draw_sel ^= 1;
+          m->draw = m->draw_buf[m->draw_sel];
+          AE_TRY(join_side(m, m->draw_sel, s));
+          a.y = m->draw;
+        } else {
+          a.comp_bn = pv.bn_vec;
+        }
+        m->pre_mode = mode;
+        m->pre_blocks = nb;
+      }
+    }
     if (conv_mfma_supported(a))
       // (the 4x4 stride-2 form, named apart, executes 4/9 of the algorithmic multiply-adds and writes the stored resolution)
       TIMED(si, st.up_dgrad ? "bwd.dgrad_mfma_stride2" : "bwd.dgrad_mfma", conv_flops,
@@ -671,6 +731,12 @@ int model_set_recompute(ae_model* m, int on) {
   if (!m) return fail(AE_EINVAL, "model_set_recompute: null model");
   m->recompute = on != 0;
   m->have_forward = false;      // a backward pass needs a forward pass taken the same way
+  return AE_OK;
+}
+
+int model_set_fused_backward(ae_model* m, int on) {
+  if (!m) return fail(AE_EINVAL, "model_set_fused_backward: null model");
+  m->fuse_bwd = on != 0;
   return AE_OK;
 }
 
@@ -805,6 +871,7 @@ int model_backward(ae_model* m, const void* params, const void* x, const void* d
   Plan& P = m->plan;
   if ((!params || !grads) && P.n_params > 0) return fail(AE_EINVAL, "model_backward: params or grads is null");
   if (!m->have_forward) return fail(AE_ESTATE, "model_backward: no forward pass on this handle to differentiate");
+  m->pre_mode = 0;
   hipStream_t s = (hipStream_t)stream;
   const float* prm = (const float*)params;
   float* gr = (float*)grads;

@@ -74,6 +74,15 @@ struct IgemmParams {
   // of the image (Wt = Wc / strips, TH = 256 / Wt); GEMM row m = tile * 256 + th * Wt + tw then is pixel
   // (row block * TH + th, strip * Wt + tw) of its image.  1: a tile spans the image width and rows are pixels in order.
   int strips = 1;
+  // Companion tensor of the output's shape and layout (interior tiles only): the saved activation a of the layer whose
+  // output gradient this launch computes.  With dyv = (a > 0 ? value : 0) per stored value:
+  //   1: dyv is stored instead of the value (ReLU backward); partial receives per-tile column sums of dyv (the bias gradient);
+  //   2: the value is stored unchanged; partial receives per-tile column sums of dyv and of dyv * xhat, with
+  //      xhat = a * invstd/scale - (shift/scale + mean) * invstd from comp_bn = [scale | shift | mean | invstd] (the sums
+  //      of a batch-norm backward behind ReLU and max-pooling; columns with scale = 0 get a zero second sum).
+  const void* comp = nullptr;
+  int comp_mode = 0;
+  const float* comp_bn = nullptr;
 };
 
 // output row (pixel index in y) of GEMM row m
@@ -142,14 +151,49 @@ template <> __device__ __forceinline__ void mma_step<float>(const uint4v& a, con
 // Epilogue of a tile that lies wholly inside the output (no bounds checks): bias, rounding to the
 // storage type, optional column statistics of the stored value, optional ReLU, then 16-byte
 // row stores staged through this wave's LDS area.
-template <typename T, int MI, int NJ, int WN, int SW, bool STATS, bool RELU, bool MXQ = false>
+// the 16/sizeof(T) values of a 16-byte chunk held in registers
+template <typename T> __device__ __forceinline__ void unpack_chunk(const uint4v& w, float (&v)[16 / (int)sizeof(T)]);
+template <> __device__ __forceinline__ void unpack_chunk<bf16_t>(const uint4v& w, float (&v)[8]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    v[2 * i] = __uint_as_float((uint32_t)w[i] << 16);
+    v[2 * i + 1] = __uint_as_float((uint32_t)w[i] & 0xFFFF0000u);
+  }
+}
+template <> __device__ __forceinline__ void unpack_chunk<float>(const uint4v& w, float (&v)[4]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) v[i] = __uint_as_float((uint32_t)w[i]);
+}
+
+// Per-lane state of the companion-tensor epilogues (IgemmParams::comp): a lane stores the same 16-byte column chunk of
+// every row it handles, so it keeps that chunk's column sums (and the two coefficients of xhat per column).
+template <int EPC> struct CompSums { float s1[EPC], s2[EPC], p1[EPC], p0[EPC]; };
+
+template <typename T, int MI, int NJ, int WN, int SW, bool STATS, bool RELU, bool MXQ = false, int COMP = 0>
 __device__ __forceinline__ void igemm_store_interior(const floatx16 (&acc)[MI][NJ], const float (&bias)[NJ], T* stage,
                                                      T* yrow, int N, int lane, float (&s1)[NJ], float (&s2)[NJ],
-                                                     const IgemmParams& p, int64_t mrow0, int phase, T* ycol) {
+                                                     const IgemmParams& p, int64_t mrow0, int phase, T* ycol,
+                                                     CompSums<16 / (int)sizeof(T)>* cs = nullptr) {
   constexpr int ES = (int)sizeof(T);
   constexpr int EPC = 16 / ES;               // elements per 16-byte chunk
   constexpr int CPRO = WN / EPC;             // chunks per staged row
   const int col_lane = lane & 31, row_lane = (lane >> 5) * 4;
+  // companion tensor: all of this wave's chunks are requested before the first row is staged, so that their
+  // latency runs behind the conversion and the stores of the rows before them
+  constexpr int NCH = (32 * CPRO) / 64;
+  uint4v cmp[COMP != 0 ? MI : 1][COMP != 0 ? NCH : 1];
+  if constexpr (COMP != 0) {
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int c = 0; c < NCH; ++c) {
+        const int idx = c * 64 + lane;
+        const int lr = idx / CPRO, ch = idx % CPRO;
+        const T* dst = (p.phases == 1 && p.strips == 1) ? yrow + (int64_t)(i * 32 + lr) * N + ch * EPC
+                                                        : ycol + igemm_out_row(p, mrow0 + i * 32 + lr, phase) * N + ch * EPC;
+        cmp[i][c] = *reinterpret_cast<const uint4v*>(reinterpret_cast<const T*>(p.comp) + (dst - reinterpret_cast<T*>(p.y)));
+      }
+  }
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
 #pragma unroll
@@ -192,6 +236,19 @@ __device__ __forceinline__ void igemm_store_interior(const floatx16 (&acc)[MI][N
                                        : (p.mx_elem == MX_INT4 ? MxFormat<MX_INT4>::quant(f[t], inv_sc, sc) : mx_quant_e2m1(f[t], inv_sc, sc));
         }
         Store<T>::stv(dst, f);
+      } else if constexpr (COMP != 0) {
+        float f[EPC], a[EPC];
+        Store<T>::ldv(&stage[lr * SW + ch * EPC], f);
+        unpack_chunk<T>(cmp[i][c], a);
+#pragma unroll
+        for (int t = 0; t < EPC; ++t) {
+          const float dyv = a[t] > 0.0f ? f[t] : 0.0f;
+          cs->s1[t] += dyv;
+          if (COMP == 2) cs->s2[t] = fmaf(dyv, fmaf(a[t], cs->p1[t], cs->p0[t]), cs->s2[t]);
+          else f[t] = dyv;
+        }
+        if (COMP == 1) Store<T>::stv(dst, f);
+        else *reinterpret_cast<uint4v*>(dst) = *reinterpret_cast<const uint4v*>(&stage[lr * SW + ch * EPC]);
       } else {
         *reinterpret_cast<uint4v*>(dst) = *reinterpret_cast<const uint4v*>(&stage[lr * SW + ch * EPC]);
       }
@@ -250,6 +307,38 @@ __device__ __forceinline__ void igemm_epilogue(floatx16 (&acc)[BM / WGM / 32][BN
       igemm_store_interior<T, MI, NJ, WN, SW, false, false, true>(acc, bias, stage, yrow, p.N, lane, s1, s2, p, mrow0, phase, ycol);
     else if constexpr (EPI == 2)
       igemm_resid_stats<T, MI, NJ>(acc, bias, (const T*)p.resid + (m0 + wm * WM) * p.N + n0 + wn * WN, p.N, lane, s1, s2);
+    else if constexpr (EPI == 3 || EPI == 4) {
+      // companion-tensor sums (EPI 3: IgemmParams::comp_mode 1, EPI 4: comp_mode 2): this lane's chunk of columns is the same in every row it stores (CPRO divides 64)
+      constexpr int EPC = 16 / ES, CPRO = WN / EPC;
+      static_assert(64 % CPRO == 0, "a lane keeps one column chunk");
+      CompSums<EPC> cs;
+      const int colc = n0 + wn * WN + (lane % CPRO) * EPC;
+#pragma unroll
+      for (int t = 0; t < EPC; ++t) {
+        cs.s1[t] = 0.0f; cs.s2[t] = 0.0f; cs.p1[t] = 0.0f; cs.p0[t] = 0.0f;
+        if (EPI == 4) {
+          const float sc = p.comp_bn[colc + t], sh = p.comp_bn[p.N + colc + t];
+          const float mu = p.comp_bn[2 * p.N + colc + t], is = p.comp_bn[3 * p.N + colc + t];
+          if (sc != 0.0f) {
+            const float inv = 1.0f / sc;
+            cs.p1[t] = is * inv;
+            cs.p0[t] = -(sh * inv + mu) * is;
+          }
+        }
+      }
+      igemm_store_interior<T, MI, NJ, WN, SW, false, false, false, EPI - 2>(acc, bias, stage, yrow, p.N, lane, s1, s2, p, mrow0, phase, ycol, &cs);
+#pragma unroll
+      for (int t = 0; t < EPC; ++t) {
+        for (int off = CPRO; off < 64; off <<= 1) {
+          cs.s1[t] += __shfl_xor(cs.s1[t], off, 64);
+          cs.s2[t] += __shfl_xor(cs.s2[t], off, 64);
+        }
+        if (lane < CPRO) {
+          sRed[wm][0][wn * WN + lane * EPC + t] = cs.s1[t];
+          sRed[wm][1][wn * WN + lane * EPC + t] = cs.s2[t];
+        }
+      }
+    }
     else if (p.partial) igemm_store_interior<T, MI, NJ, WN, SW, true, false>(acc, bias, stage, yrow, p.N, lane, s1, s2, p, mrow0, phase, ycol);
     else if (p.act == ACT_RELU) igemm_store_interior<T, MI, NJ, WN, SW, false, true>(acc, bias, stage, yrow, p.N, lane, s1, s2, p, mrow0, phase, ycol);
     else igemm_store_interior<T, MI, NJ, WN, SW, false, false>(acc, bias, stage, yrow, p.N, lane, s1, s2, p, mrow0, phase, ycol);
@@ -291,7 +380,7 @@ __device__ __forceinline__ void igemm_epilogue(floatx16 (&acc)[BM / WGM / 32][BN
       }
     }
   }
-  if (p.partial) {
+  if (p.partial && EPI != 3 && EPI != 4) {
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
       float t1 = s1[j] + __shfl_xor(s1[j], 32, 64);
@@ -739,7 +828,7 @@ constexpr int passes_before(int passes, int tap) {
 }
 constexpr int vm_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }   // s_waitcnt vmcnt(n) only
 
-template <typename T, int BN, int WGM, int WGN, int W, bool INTERIOR>
+template <typename T, int BN, int WGM, int WGN, int W, bool INTERIOR, int EPI = 0>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k_conv3_patch(IgemmParams p) {
   static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
   constexpr int ES = (int)sizeof(T);
@@ -900,7 +989,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
 #undef PATCH_DMA
 #undef WEIGHT_DMA
   __syncthreads();                               // every wave is done with the operands: the epilogue reuses the memory
-  igemm_epilogue<T, BM, BN, WGM, WGN, INTERIOR>(acc, p, smem, sRed, m0, n0, (int64_t)tile_m);
+  igemm_epilogue<T, BM, BN, WGM, WGN, INTERIOR, EPI>(acc, p, smem, sRed, m0, n0, (int64_t)tile_m);
 }
 
 struct IgemmTile { int bm, bn, bkb; };
@@ -1029,6 +1118,24 @@ bool conv_up_dgrad_usable(const ConvArgs& a0) {
   return conv_mfma_supported(a);
 }
 
+// Number of row blocks whose column sums a launch with a companion tensor (ConvArgs::comp) leaves in `partial`, or 0
+// if this launch cannot take one: the epilogue exists for bfloat16 launches whose tiles all lie inside the output,
+// without split-K and without an epilogue variant of their own.
+int conv_comp_blocks(const ConvArgs& a0) {
+  if (a0.dtype != AE_BF16 || !conv_mfma_supported(a0) || a0.epi != CONV_EPI_NONE || a0.tri != 0 || a0.geom == CONV_UP_PHASES ||
+      a0.y_aux || a0.act != ACT_NONE || a0.bias)
+    return 0;
+  const ConvArgs a = conv_effective(a0);
+  const int64_t M = (int64_t)a.n * a.hc * a.wc;
+  if (conv3_patch_usable(a0)) return (int)(M / 256);
+  const IgemmTile t = pick_tile(M, a.cout, a.cin, 2, a0.geom == CONV_PLAIN, 256);
+  if (t.bn == 256 || M % t.bm != 0 || a.cout % t.bn != 0) return 0;
+  ConvArgs probe = a0;
+  probe.partial = reinterpret_cast<float*>(1);     // only null / non-null matters: statistics keep K in one piece
+  if (conv_mfma_splits(probe) != 1) return 0;
+  return (int)(M / t.bm);
+}
+
 int launch_conv_mfma(const ConvArgs& a0, hipStream_t s) {
   if (!conv_mfma_supported(a0)) return fail(AE_EINVAL, "conv_mfma: shape not supported");
   if (a0.geom == CONV_UP_PHASES && !conv_up_phases_usable(a0)) return fail(AE_EINVAL, "conv_mfma: phase form not usable here");
@@ -1042,6 +1149,12 @@ int launch_conv_mfma(const ConvArgs& a0, hipStream_t s) {
   p.Hc = a.hc; p.Wc = a.wc; p.Cin = a.cin; p.ksz = a.k; p.up = a.up; p.act = a.act;
   p.Hv = a.hc; p.Wv = a.wc; p.stride = 1; p.pad = (a.k - 1) >> 1; p.phases = 1;
   p.resid = a0.resid;
+  p.comp = a0.comp; p.comp_mode = a0.comp_mode; p.comp_bn = a0.comp_bn;
+  if (a0.comp_mode != 0) {
+    if (a0.comp_mode < 1 || a0.comp_mode > 2 || !a0.comp || !a0.partial || (a0.comp_mode == 2 && !a0.comp_bn) ||
+        conv_comp_blocks(a0) == 0)
+      return fail(AE_EINVAL, "conv_mfma: companion-tensor epilogue not usable for this launch");
+  }
   p.mx_block = a0.mx_block;
   p.mx_elem = a0.mx_elem;
   p.tri = a0.tri;
@@ -1067,11 +1180,17 @@ int launch_conv_mfma(const ConvArgs& a0, hipStream_t s) {
     p.tiles_n = a.cout / bn;
     p.strips = a.wc > 64 ? a.wc / 64 : 1;
     dim3 pgrid((unsigned)((p.M / 256) * p.tiles_n));
-#define PATCH_LAUNCH_W(T, WV)                                                                             \
-  do {                                                                                                   \
-    if (bn == 128) hipLaunchKernelGGL((k_conv3_patch<T, 128, 2, 2, WV, true>), pgrid, dim3(256), 0, s, p); \
-    else hipLaunchKernelGGL((k_conv3_patch<T, 64, 4, 1, WV, true>), pgrid, dim3(256), 0, s, p);           \
+#define PATCH_LAUNCH_E(T, WV, E)                                                                             \
+  do {                                                                                                      \
+    if (bn == 128) hipLaunchKernelGGL((k_conv3_patch<T, 128, 2, 2, WV, true, E>), pgrid, dim3(256), 0, s, p); \
+    else hipLaunchKernelGGL((k_conv3_patch<T, 64, 4, 1, WV, true, E>), pgrid, dim3(256), 0, s, p);           \
   } while (0)
+#define PATCH_LAUNCH_W(T, WV) PATCH_LAUNCH_E(T, WV, 0)
+    if (a0.comp_mode != 0) {            // (conv_comp_blocks: bfloat16 only)
+      if (a0.comp_mode == 1) { if (a.wc == 16) PATCH_LAUNCH_E(bf16_t, 16, 3); else if (a.wc == 32) PATCH_LAUNCH_E(bf16_t, 32, 3); else PATCH_LAUNCH_E(bf16_t, 64, 3); }
+      else { if (a.wc == 16) PATCH_LAUNCH_E(bf16_t, 16, 4); else if (a.wc == 32) PATCH_LAUNCH_E(bf16_t, 32, 4); else PATCH_LAUNCH_E(bf16_t, 64, 4); }
+      return launch_status("conv3_patch");
+    }
 #define PATCH_LAUNCH(T)                                     \
   do {                                                      \
     if (a.wc == 16) PATCH_LAUNCH_W(T, 16);                  \
@@ -1082,6 +1201,7 @@ int launch_conv_mfma(const ConvArgs& a0, hipStream_t s) {
     else PATCH_LAUNCH(float);
 #undef PATCH_LAUNCH
 #undef PATCH_LAUNCH_W
+#undef PATCH_LAUNCH_E
     return launch_status("conv3_patch");
   }
   // the wide tile exists without run-time checks only; tiles of very different K lengths (the triangular modes 1-3)
@@ -1117,6 +1237,20 @@ int launch_conv_mfma(const ConvArgs& a0, hipStream_t s) {
     if (a.dtype == AE_BF16) IGEMM_LAUNCH_T(bf16_t, BMV, BNV, GM, GN);          \
     else IGEMM_LAUNCH_T(float, BMV, BNV, GM, GN);                              \
   } while (0)
+  if (a0.comp_mode != 0) {
+    // (conv_comp_blocks: bfloat16, interior tiles, no split, not the eight-wavefront tile)
+#define IGEMM_LAUNCH_COMP(BMV, BNV, GM, GN)                                                                           \
+  do {                                                                                                                \
+    if (a0.comp_mode == 1) hipLaunchKernelGGL((k_igemm<bf16_t, BMV, BNV, GM, GN, 64, true, true, 3>), grid, dim3(256), 0, s, p); \
+    else hipLaunchKernelGGL((k_igemm<bf16_t, BMV, BNV, GM, GN, 64, true, true, 4>), grid, dim3(256), 0, s, p);         \
+  } while (0)
+    if (t.bm == 256 && t.bn == 128) IGEMM_LAUNCH_COMP(256, 128, 2, 2);
+    else if (t.bm == 256) IGEMM_LAUNCH_COMP(256, 64, 4, 1);
+    else if (t.bn == 128) IGEMM_LAUNCH_COMP(128, 128, 2, 2);
+    else IGEMM_LAUNCH_COMP(128, 64, 2, 2);
+#undef IGEMM_LAUNCH_COMP
+    return launch_status("conv_mfma_comp");
+  }
   if (a0.epi != CONV_EPI_NONE) {
     // (conv_epi_usable: interior tiles, BN = 128, no split)
 #define IGEMM_LAUNCH_EPI(T, BMV, E) hipLaunchKernelGGL((k_igemm<T, BMV, 128, 2, 2, 64, true, true, E>), grid, dim3(256), 0, s, p)

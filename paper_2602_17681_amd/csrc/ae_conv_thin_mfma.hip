@@ -534,6 +534,11 @@ __device__ __forceinline__ void thin_patch_store(const ThinPatchRegs& R, bf16_t*
 //           pooled gradient at the window's winner where its pre-activation is positive
 //   PASS 3  dx_k = scale*(dy_k - c1 - xhat_k*c2), rounded to storage, kept in LDS as the pixel-major slab
 //           the weight-gradient MFMAs of k_thin_wgrad_mfma read: partial[block][CW][64]
+//   PASS 4  (not a first layer: the LAST layer's input gradient through its x2 upsample, flipped weights, no bias)
+//           out[n][H/2][W/2][CW] = the 2x2 sums of the convolution as k_thin_in_mfma with UPSUM forms them, stored
+//           as the ReLU backward of the layer below wants them: zero where that layer's saved activation
+//           `dout` [n][H/2][W/2][CW] is not positive; partial[block][0][CW] = column sums of what was stored
+//           (the bias gradient of the layer below)
 // Rounding to storage and x -> scale*x + shift are monotonic, so the window's maximum activation is
 // relu(scale*x_w + shift) with x_w the rounded maximum of the window for scale > 0, the minimum for
 // scale < 0, x_0 for scale = 0 (all equal: the first wins) — passes 1 and 2 need nothing else of the
@@ -558,9 +563,9 @@ __global__ __launch_bounds__(NT, PASS == 3 ? 2 : 1) void k_thin_first(
   constexpr int GCH = 64 * CPR;                 // chunks of the pooled-gradient tile (64 windows)
   constexpr int GPT = (GCH + NT - 1) / NT;
   __shared__ __attribute__((aligned(16))) bf16_t tile[MAXT * 4];
-  __shared__ __attribute__((aligned(16))) bf16_t sG[PASS >= 2 ? 64 * CW : 8];
-  __shared__ __attribute__((aligned(16))) bf16_t sW[PASS == 3 ? NT * LA : (PASS == 1 ? 4 * 8 * SW : 8)];
-  __shared__ float sRed[(PASS == 0 || PASS == 2) ? 4 * 2 * CW : 1];
+  __shared__ __attribute__((aligned(16))) bf16_t sG[(PASS == 2 || PASS == 3) ? 64 * CW : 8];
+  __shared__ __attribute__((aligned(16))) bf16_t sW[PASS == 3 ? NT * LA : ((PASS == 1 || PASS == 4) ? 4 * 8 * SW : 8)];
+  __shared__ float sRed[(PASS == 0 || PASS == 2 || PASS == 4) ? 4 * 2 * CW : 1];
   const int TH = NT >> tw_shift;
   const int PW = TW + 4;
   const int Hq = H >> 1, Wq = W >> 1;
@@ -578,10 +583,10 @@ __global__ __launch_bounds__(NT, PASS == 3 ? 2 : 1) void k_thin_first(
   for (int j = 0; j < NJ; ++j) {
     const int c = j * 32 + col_lane;
     bs[j] = bias ? bias[c] : 0.0f;
-    sc[j] = PASS >= 1 ? bn_vec[c] : 1.0f;
-    sh[j] = PASS >= 1 ? bn_vec[CW + c] : 0.0f;
-    mu[j] = PASS >= 2 ? bn_vec[2 * CW + c] : 0.0f;
-    is[j] = PASS >= 2 ? bn_vec[3 * CW + c] : 1.0f;
+    sc[j] = (PASS >= 1 && PASS <= 3) ? bn_vec[c] : 1.0f;
+    sh[j] = (PASS >= 1 && PASS <= 3) ? bn_vec[CW + c] : 0.0f;
+    mu[j] = (PASS == 2 || PASS == 3) ? bn_vec[2 * CW + c] : 0.0f;
+    is[j] = (PASS == 2 || PASS == 3) ? bn_vec[3 * CW + c] : 1.0f;
     const float c1 = PASS == 3 ? bn_vec[4 * CW + c] : 0.0f;
     const float c2 = PASS == 3 ? bn_vec[5 * CW + c] : 0.0f;
     al[j] = -(sc[j] * c2) * is[j];
@@ -606,12 +611,22 @@ __global__ __launch_bounds__(NT, PASS == 3 ? 2 : 1) void k_thin_first(
   };
   ThinPatchRegs pre;
   static_assert(GPT <= 2, "pooled-gradient tile: at most two chunks per thread");
-  uint4 gv0 = make_uint4(0u, 0u, 0u, 0u), gv1 = gv0;
+  uint4 gv0 = make_uint4(0u, 0u, 0u, 0u), gv1 = gv0;   // pass 4: this lane's chunks of the companion tensor for i = 0, 1
+  float cs[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};   // pass 4: column sums of this lane's chunk
   auto prefetch = [&](int t) {
     int n, h0, w0;
     where(t, n, h0, w0);
     thin_patch_load(pre, thin + (int64_t)n * CT * H * W, H, W, CT, h0 - 1, w0, TH + 2, TW);
-    if (PASS >= 2) {
+    if (PASS == 4) {
+      static_assert(8 * CPR <= 64, "one chunk per lane and row group");
+      auto chunk = [&](int i) {
+        const int G = wave * 16 + i * 8 + min(lane, 8 * CPR - 1) / CPR, ch = lane % CPR;
+        const int hq = (h0 >> 1) + (G >> (tw_shift - 1)), wq = (w0 >> 1) + (G & ((TW >> 1) - 1));
+        return *reinterpret_cast<const uint4*>(dout + (((int64_t)n * Hq + hq) * Wq + wq) * CW + ch * 8);
+      };
+      gv0 = chunk(0);
+      gv1 = chunk(1);
+    } else if (PASS >= 2) {
       auto chunk = [&](int idx) {
         const int G = idx / CPR, ch = idx % CPR;
         const int hq = (h0 >> 1) + (G >> (tw_shift - 1)), wq = (w0 >> 1) + (G & ((TW >> 1) - 1));
@@ -628,7 +643,8 @@ __global__ __launch_bounds__(NT, PASS == 3 ? 2 : 1) void k_thin_first(
     where(t, n, h0, w0);
     __syncthreads();                            // the previous patch is fully consumed
     thin_patch_store(pre, tile, H, W, CT, h0 - 1, w0, TH + 2, TW);
-    if (PASS >= 2) {
+    uint4 cm0 = gv0, cm1 = gv1;                 // (pass 4: the prefetch below overwrites gv0, gv1)
+    if (PASS == 2 || PASS == 3) {
       if (tid < GCH) *reinterpret_cast<uint4*>(&sG[tid * 8]) = gv0;
       if (GPT == 2 && NT + tid < GCH) *reinterpret_cast<uint4*>(&sG[(NT + tid) * 8]) = gv1;
     }
@@ -657,7 +673,7 @@ __global__ __launch_bounds__(NT, PASS == 3 ? 2 : 1) void k_thin_first(
       }
     }
 
-    bf16_t* stage = sW + wave * (8 * SW);        // PASS 1 only
+    bf16_t* stage = sW + wave * (8 * SW);        // passes 1 and 4
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
 #pragma unroll
@@ -674,6 +690,9 @@ __global__ __launch_bounds__(NT, PASS == 3 ? 2 : 1) void k_thin_first(
               s1[j] += d;
               s2[j] = fmaf(d, d, s2[j]);
             }
+          } else if (PASS == 4) {
+            // input gradient through the x2 upsample: the sum over the 2x2 group (k_thin_in_mfma with UPSUM)
+            stage[(eg * 2 + g) * SW + j * 32 + col_lane] = f32_to_bf16((x[0] + x[1]) + (x[2] + x[3]));
           } else if (PASS <= 2) {
             const float hi = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
             const float lo = fminf(fminf(x[0], x[1]), fminf(x[2], x[3]));
@@ -709,6 +728,28 @@ __global__ __launch_bounds__(NT, PASS == 3 ? 2 : 1) void k_thin_first(
               dst[((k >> 1) * TW + (k & 1)) * LA] = f32_to_bf16(o);
             }
           }
+        }
+      }
+      if (PASS == 4) {
+        // ReLU backward of the layer below while storing: its saved activation decides, column sums for its bias
+        bf16_t* out_n = out + (int64_t)n * Hq * Wq * CW;
+        if (lane < 8 * CPR) {
+          const int g8 = lane / CPR, ch = lane % CPR;
+          const int G = wave * 16 + i * 8 + g8;
+          const int hq = (h0 >> 1) + (G >> (tw_shift - 1)), wq = (w0 >> 1) + (G & ((TW >> 1) - 1));
+          const uint4 sv = *reinterpret_cast<const uint4*>(&stage[g8 * SW + ch * 8]);
+          const uint4 av = i == 0 ? cm0 : cm1;
+          const uint32_t sw[4] = {sv.x, sv.y, sv.z, sv.w}, aw[4] = {av.x, av.y, av.z, av.w};
+          uint32_t ow[4];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const float a_lo = __uint_as_float(aw[q] << 16), a_hi = __uint_as_float(aw[q] & 0xFFFF0000u);
+            const uint32_t lo = a_lo > 0.0f ? (sw[q] & 0xFFFFu) : 0u, hi = a_hi > 0.0f ? (sw[q] & 0xFFFF0000u) : 0u;
+            cs[2 * q] += __uint_as_float(lo << 16);
+            cs[2 * q + 1] += __uint_as_float(hi);
+            ow[q] = lo | hi;
+          }
+          *reinterpret_cast<uint4*>(out_n + ((int64_t)hq * Wq + wq) * CW + ch * 8) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
         }
       }
       if (PASS == 1) {
@@ -754,12 +795,22 @@ __global__ __launch_bounds__(NT, PASS == 3 ? 2 : 1) void k_thin_first(
     }
   }
 
-  if (PASS == 0 || PASS == 2) {
+  if (PASS == 4) {
+    // lanes that share a column chunk differ in lane / CPR (lanes beyond 8*CPR hold zeros)
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) {
-      const float t1 = s1[j] + __shfl_xor(s1[j], 32, 64);
-      const float t2 = s2[j] + __shfl_xor(s2[j], 32, 64);
-      if (lane < 32) { sRed[(wave * 2 + 0) * CW + j * 32 + col_lane] = t1; sRed[(wave * 2 + 1) * CW + j * 32 + col_lane] = t2; }
+    for (int t = 0; t < 8; ++t) {
+      for (int off = CPR; off < 64; off <<= 1) cs[t] += __shfl_xor(cs[t], off, 64);
+      if (lane < CPR) { sRed[(wave * 2 + 0) * CW + lane * 8 + t] = cs[t]; sRed[(wave * 2 + 1) * CW + lane * 8 + t] = 0.0f; }
+    }
+  }
+  if (PASS == 0 || PASS == 2 || PASS == 4) {
+    if (PASS != 4) {
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) {
+        const float t1 = s1[j] + __shfl_xor(s1[j], 32, 64);
+        const float t2 = s2[j] + __shfl_xor(s2[j], 32, 64);
+        if (lane < 32) { sRed[(wave * 2 + 0) * CW + j * 32 + col_lane] = t1; sRed[(wave * 2 + 1) * CW + j * 32 + col_lane] = t2; }
+      }
     }
     __syncthreads();
     for (int i = tid; i < 2 * CW; i += NT)
@@ -980,17 +1031,20 @@ int thin_first_blocks(int n, int h, int w, int pass) { return thin_first_grid(th
 // pass 0: partial <- column statistics (packs wfrag from wcanon first);  pass 1: out <- pooled activation;
 // pass 2: partial <- batch-norm backward sums from the pooled gradient dout;
 // pass 3: workspace, dw_canonical <- weight gradient.  Passes 1-3 read the wfrag an earlier pass 0 / pack left.
+// pass 4 (last layer's input gradient, see k_thin_first): thin = the planar output gradient, wcanon = the layer's
+// weights [ct][cw][3][3] (packed flipped), dout = saved activation of the layer below, out <- masked gradient,
+// partial <- column sums ([blocks][2][cw], second row zero).
 int launch_thin_first(int pass, const void* thin, const float* wcanon, void* wfrag, const float* bias,
                       const float* bn_vec, const void* dout, void* out, float* partial, float* dw_canonical, int n, int h,
                       int w, int ct, int cw, hipStream_t s) {
-  if (pass < 0 || pass > 3 || !thin_first_supported(ct, cw, 3, 0, AE_BF16, h, w))
+  if (pass < 0 || pass > 4 || !thin_first_supported(ct, cw, 3, 0, AE_BF16, h, w))
     return fail(AE_EINVAL, "thin_first: shape not supported");
   if (((uintptr_t)thin & 15) != 0) return fail(AE_EINVAL, "thin_first: input must be 16-byte aligned");
   const ThinTile t = thin_tile(n, h, w);
   const int nj = cw / 32;
   if (wcanon) {
     hipLaunchKernelGGL(k_thin_pack_wfrag, dim3((unsigned)((nj * 32 * 48 + NT - 1) / NT)), dim3(NT), 0, s, wcanon,
-                       (bf16_t*)wfrag, ct, cw, nj * 32, 0);
+                       (bf16_t*)wfrag, ct, cw, nj * 32, pass == 4 ? 1 : 0);
     AE_TRY(launch_status("thin_pack_wfrag"));
   }
   const int grid = thin_first_grid(t.blocks, pass);
@@ -1004,7 +1058,8 @@ int launch_thin_first(int pass, const void* thin, const float* wcanon, void* wfr
     case 0: LAUNCH_TF_NJ(0); break;
     case 1: LAUNCH_TF_NJ(1); break;
     case 2: LAUNCH_TF_NJ(2); break;
-    default: LAUNCH_TF_NJ(3); break;
+    case 3: LAUNCH_TF_NJ(3); break;
+    default: LAUNCH_TF_NJ(4); break;
   }
 #undef LAUNCH_TF_NJ
 #undef LAUNCH_TF

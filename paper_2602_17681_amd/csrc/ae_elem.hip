@@ -428,16 +428,38 @@ __global__ void k_post_bwd_reduce(const T* __restrict__ raw, const T* __restrict
 }
 
 // one block per channel: dgamma = sum dy*xhat, dbeta = sum dy; c1 = dbeta/M, c2 = dgamma/M (batch statistics)
+// fix_raw / fix_dout (bfloat16 [n][H][W][C] and [n][H>>pool][W>>pool][C], optional): the partials came from an
+// epilogue that derives xhat from the saved ReLU output, which a channel of scale 0 does not allow; such a channel's
+// sums are taken here from the definition (all pre-activations equal the shift: the first position of a window wins
+// and passes the gradient if the shift is positive).
 __global__ void k_bn_bwd_finalize(const float* __restrict__ partial, int nblocks, double inv_rows, int C,
                                   float* __restrict__ bn_vec, float* __restrict__ dgamma_dbeta,
-                                  float* __restrict__ dbias, int batch_stats, int stored_slots) {
+                                  float* __restrict__ dbias, int batch_stats, int stored_slots,
+                                  const bf16_t* __restrict__ fix_raw, const bf16_t* __restrict__ fix_dout, int64_t n,
+                                  int H, int W, int pool) {
   __shared__ double sm[NT / 64 + 1];
   const int c = blockIdx.x;
   double s1 = 0.0, s2 = 0.0;
+  if (fix_raw && bn_vec[c] == 0.0f) {
+    if (bn_vec[C + c] > 0.0f) {
+      const int Ho = H >> pool, Wo = W >> pool;
+      const float mu = bn_vec[2 * C + c], is = bn_vec[3 * C + c];
+      for (int64_t r = threadIdx.x; r < n * Ho * Wo; r += NT) {
+        const int wo = (int)(r % Wo);
+        const int ho = (int)((r / Wo) % Ho);
+        const int64_t b = r / ((int64_t)Wo * Ho);
+        const float g = bf16_to_f32(fix_dout[r * C + c]);
+        const float x = bf16_to_f32(fix_raw[((b * H + ((int64_t)ho << pool)) * W + ((int64_t)wo << pool)) * C + c]);
+        s1 += (double)g;
+        s2 += (double)(g * ((x - mu) * is));
+      }
+    }
+  } else {
 #pragma unroll 8
-  for (int b = threadIdx.x; b < nblocks; b += NT) {
-    s1 += (double)partial[((int64_t)b * 2) * C + c];
-    s2 += (double)partial[((int64_t)b * 2 + 1) * C + c];
+    for (int b = threadIdx.x; b < nblocks; b += NT) {
+      s1 += (double)partial[((int64_t)b * 2) * C + c];
+      s2 += (double)partial[((int64_t)b * 2 + 1) * C + c];
+    }
   }
   s1 = block_sum<NT>(s1, sm);
   s2 = block_sum<NT>(s2, sm);
@@ -816,9 +838,11 @@ int launch_post_bwd_reduce(const void* raw, const void* dout, const void* out_ac
 }
 
 int launch_bn_bwd_finalize(const float* partial, int nblocks, int64_t rows, int c, float* dbias, float* bn_vec,
-                           float* dgamma_dbeta, int batch_stats, hipStream_t s) {
+                           float* dgamma_dbeta, int batch_stats, hipStream_t s, const void* fix_raw, const void* fix_dout,
+                           int64_t n, int h, int w, int pool) {
   hipLaunchKernelGGL(k_bn_bwd_finalize, dim3(c), dim3(NT), 0, s, partial, nblocks, 1.0 / (double)rows, c, bn_vec,
-                     dgamma_dbeta, dbias, batch_stats, batch_stats ? 0 : 1);
+                     dgamma_dbeta, dbias, batch_stats, batch_stats ? 0 : 1, (const bf16_t*)fix_raw, (const bf16_t*)fix_dout,
+                     n, h, w, pool);
   return launch_status("bn_bwd_finalize");
 }
 

@@ -150,6 +150,13 @@ struct ConvArgs {
   //                   (x = dY [n][hc][wc][cin], y = dX [n][hc/2][wc/2][cout], w = [cout][4][4][cin]),
   //                   which also replaces the 2x2 sum over each upsampled pixel.
   int geom = 0;
+  // Companion tensor (see IgemmParams::comp in ae_conv_mfma.hip): the saved activation of the layer whose output
+  // gradient this launch computes, same shape and layout as y.  comp_mode 1: y receives the ReLU-masked gradient and
+  // partial its column sums; 2: y unchanged, partial receives the two sums of a batch-norm backward behind ReLU (+ pool),
+  // comp_bn = [scale | shift | mean | invstd].  Usable where conv_comp_blocks() > 0 (= the row blocks written to partial).
+  const void* comp = nullptr;
+  int comp_mode = 0;
+  const float* comp_bn = nullptr;
   // Dense-GEMM epilogues (k = 1 layers whose tiles all lie inside the output, no split-K):
   //   CONV_EPI_MXQ    the stored output is MX block-quantised (blocks of mx_block columns, a power of two between the
   //                   elements of 16 bytes and 64; FP4 E2M1 elements);
@@ -184,6 +191,7 @@ enum { CONV_PLAIN = 0, CONV_UP_PHASES = 1, CONV_UP_DGRAD = 2 };
 enum { CONV_EPI_NONE = 0, CONV_EPI_MXQ = 1, CONV_EPI_RESID = 2 };
 bool conv_epi_usable(const ConvArgs& a);         // can launch_conv_mfma run a.epi for this shape?
 bool conv_up_phases_usable(const ConvArgs& a);   // a: the plain description (geom ignored)
+int conv_comp_blocks(const ConvArgs& a);
 bool conv_up_dgrad_usable(const ConvArgs& a);    // a: the plain description of the input-gradient conv at conv resolution
 // Summed weights of the two forms above from the canonical [cout][cin][3][3] fp32 weights.
 int launch_pack_weights_up(const float* w, void* wp, int cout, int cin, int dtype, int geom, hipStream_t s);
@@ -247,7 +255,8 @@ int launch_post_forward(const void* raw, const float* bn_vec, void* out, int64_t
 int launch_post_bwd_reduce(const void* raw, const void* dout, const void* out_act, const float* bn_vec, int64_t n, int h,
                            int w, int c, int act, int pool, int dtype, float* partial, hipStream_t s);
 int launch_bn_bwd_finalize(const float* partial, int nblocks, int64_t rows, int c, float* dbias, float* bn_vec,
-                           float* dgamma_dbeta, int batch_stats, hipStream_t s);
+                           float* dgamma_dbeta, int batch_stats, hipStream_t s, const void* fix_raw = nullptr,
+                           const void* fix_dout = nullptr, int64_t n = 0, int h = 0, int w = 0, int pool = 0);
 int launch_act_bwd_colsum(const void* out, const float* out_f32, const void* dout, void* draw, int64_t rows, int c,
                           int act, int dtype, float* partial, hipStream_t s);
 int launch_post_bwd_apply(const void* raw, const void* dout, const float* bn_vec, void* draw, int64_t n, int h, int w,

@@ -296,6 +296,72 @@ def test_first_layer_conv_output_recomputed_not_stored(ae, case, bn_mode):
     assert_close(res[0][3], res[1][3], 1e-2, "gradients, recomputed against stored", tol_max=5e-2)
 
 
+FUSED_BACKWARD = [
+    # conv + relu and conv + bn + relu (+ pool2) layers whose backward sums / masks are taken by the epilogue of the
+    # input-gradient kernel of the layer above: LDS-patch kernel (256 tiles at 32 x 32), 1x1 layer, stride-2 forms
+    ("in:3x32x32,conv3:64,relu,conv3:64,relu,conv3:64,bn,relu,conv3:64,bn,relu,pool2,conv1:64,pnorm,awgn,conv1:64,relu,"
+     "up2,conv3:3,sigmoid", 64),
+    ("in:3x32x32,conv3:64,bn,relu,pool2,conv3:128,bn,relu,pool2,conv3:128,bn,relu,pool2,conv1:64,pnorm,awgn,conv1:128,relu,"
+     "up2,conv3:128,relu,up2,conv3:64,relu,up2,conv3:3,sigmoid", 32),
+]
+
+
+def _with_dead_bn_channels(spec, params, bn_mode=0):
+    """gamma = 0 (and a positive, resp. negative beta) in two channels of every batch-norm layer."""
+    ent, _, _, _ = wl.param_layout(spec, bn_mode)
+    p = params.copy()
+    for e in ent:
+        if e["kind"] == "gamma":
+            p[e["offset"] + 1] = 0.0
+            p[e["offset"] + 5] = 0.0
+        if e["kind"] == "beta":
+            p[e["offset"] + 1] = 0.75
+            p[e["offset"] + 5] = -0.5
+    return p
+
+
+@pytest.mark.parametrize("case", range(len(FUSED_BACKWARD)))
+@pytest.mark.parametrize("dead", [False, True])
+def test_fused_backward_epilogues(ae, case, dead):
+    """The ReLU backward + bias sums of conv + relu layers and the two batch-norm backward sums of conv + bn + relu
+    (+ pool2) layers come out of the epilogue of the kernel that writes the layer's output gradient: parity of every
+    gradient against the oracle (counted-decisions bar), the separate passes are gone from the timing slots, and
+    with model_set_fused_backward(0) the same library gives the same gradients up to the order of the sums.
+    dead = True: batch-norm channels with gamma = 0, whose normalised input cannot be derived from the saved
+    activation (the finalize kernel takes their sums from the definition)."""
+    import torch
+    spec, batch = FUSED_BACKWARD[case]
+    params = wl.make_params(spec, 80 + case, perturb=True, bf16=True)
+    if dead:
+        params = _with_dead_bn_channels(spec, params)
+    run_case(spec, batch, dtype="bf16", seed=80 + case, snr_db=9.0, backward=True, params=params, flips=True,
+             tag="fused backward %d dead=%s" % (case, dead))
+    m = ae.Model(spec, batch, ae.AE_BF16)
+    p = torch.from_numpy(params).cuda()
+    x = torch.from_numpy(wl.make_input(spec, batch, 80 + case, bf16=True)).cuda().to(torch.bfloat16)
+    y = torch.empty((batch,) + m.out_shape, dtype=torch.bfloat16, device="cuda")
+    dy, loss = torch.empty_like(y), torch.zeros(1, device="cuda")
+    res, slots = [], []
+    for on in (1, 0, 1):
+        m.model_set_fused_backward(on)
+        m.model_timing_reset()
+        m.model_timing_enable(True)
+        m.model_forward(p, x, 9.0, 80 + case, y)
+        ae.model_loss_mse(y, x, loss, dy)
+        g = torch.full((m.n_params,), float("nan"), device="cuda")
+        m.model_backward(p, x, dy, g)
+        m.model_timing_enable(False)
+        slots.append(sorted(t["name"].split(".", 1)[1] for t in m.model_timing_read() if t["launches"] and ".bwd." in t["name"]))
+        res.append(g.cpu().numpy())
+    m.close()
+    assert np.array_equal(res[0], res[2])
+    assert_close(res[0], res[1], 1e-4, "gradients, fused epilogues against separate passes", tol_max=1e-3)
+    import collections
+    gone = collections.Counter(slots[1]) - collections.Counter(slots[0])
+    want = {0: (2, 2), 1: (2, 3)}[case]          # (bn_reduce passes, act_colsum passes) the epilogues replace
+    assert gone["bwd.bn_reduce"] == want[0] and gone["bwd.act_colsum"] == want[1], (gone, slots)
+
+
 def test_inference_mode_of_a_network_without_a_fused_path(ae):
     """Inference mode changes nothing for a network that has no special path: same bits as the default mode."""
     import torch
