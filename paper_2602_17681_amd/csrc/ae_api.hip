@@ -297,8 +297,8 @@ int forward_conv(ae_model* m, int si, Step& st, const float* params, const void*
             launch_thin_first(0, in, wsrc, st.wpack, a.bias, nullptr, nullptr, nullptr, m->partial, nullptr, P.batch, st.hc,
                               st.wc, st.cin, st.cout, s));
       wsrc = nullptr;   // packed by the statistics pass
-      TIMED(si, "fwd.bn_finalize", 0.0, (double)thin_first_blocks(P.batch, st.hc, st.wc, 0) * 2 * st.cout * 4,
-            launch_bn_finalize(m->partial, thin_first_blocks(P.batch, st.hc, st.wc, 0), rows, st.cout, gb, nullptr, a.bias,
+      TIMED(si, "fwd.bn_finalize", 0.0, (double)thin_first_blocks(P.batch, st.hc, st.wc, st.cout, 0) * 2 * st.cout * 4,
+            launch_bn_finalize(m->partial, thin_first_blocks(P.batch, st.hc, st.wc, st.cout, 0), rows, st.cout, gb, nullptr, a.bias,
                                st.bn_vec, s));
     } else {
       TIMED(si, "fwd.bn_finalize", 0.0, 0.0,
@@ -372,7 +372,7 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
   if (st.recompute && m->recompute) {
     // sums of the batch-norm backward and the weight gradient, each from the recomputed conv output; the
     // conv-output gradient exists only as LDS slabs inside the second kernel
-    const int nb = thin_first_blocks(P.batch, st.hc, st.wc, 2);
+    const int nb = thin_first_blocks(P.batch, st.hc, st.wc, st.cout, 2);
     TIMED(si, "bwd.thin_first_sums", conv_flops, (in_el + out_el) * es,
           launch_thin_first(2, in, nullptr, st.wpack, params + st.b_off, st.bn_vec, g, nullptr, m->partial, nullptr, P.batch,
                             st.hc, st.wc, st.cin, st.cout, s));
@@ -507,7 +507,7 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
               launch_thin_first(4, dr, params + st.w_off, st.wpack_d, nullptr, nullptr, pv.out, m->draw, m->partial, nullptr,
                                 P.batch, st.hc, st.wc, st.cout, st.cin, s));
         m->pre_mode = 1;
-        m->pre_blocks = thin_first_blocks(P.batch, st.hc, st.wc, 4);
+        m->pre_blocks = thin_first_blocks(P.batch, st.hc, st.wc, st.cin, 4);
       }
     }
     if (st.needs_dx && !with_relu) {

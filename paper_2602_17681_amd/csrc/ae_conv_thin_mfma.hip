@@ -546,7 +546,8 @@ __device__ __forceinline__ void thin_patch_store(const ThinPatchRegs& R, bf16_t*
 // k whose pre-activation equals the maximum, and evaluates dx_k as alpha*x_k + beta (+ scale*dy at the
 // winner) with alpha = -scale*c2*invstd, beta = scale*(c2*invstd*mean - c1): the formula of
 // k_post_bwd_apply up to binary32 rounding, before the rounding to storage.
-// Patches are interior (H, W multiples of the patch), CW = 32*NJ, the input 16-byte aligned with
+// Patches are interior (H, W multiples of the patch); a workgroup computes CW = 32*NJ of the layer's CWT wide
+// channels (blockIdx.y selects which: 128 channels run as two halves), the input is 16-byte aligned with
 // W % 8 == 0; a workgroup walks over patches t = blockIdx.x, blockIdx.x + gridDim.x, ... and has the
 // next patch's global loads in flight while it computes.
 // ---------------------------------------------------------------------------
@@ -554,7 +555,8 @@ template <int NJ, int PASS>
 __global__ __launch_bounds__(NT, PASS == 3 ? 2 : 1) void k_thin_first(
     const bf16_t* __restrict__ thin, const bf16_t* __restrict__ wfrag, const float* __restrict__ bias,
     const float* __restrict__ bn_vec, const bf16_t* __restrict__ dout, bf16_t* __restrict__ out,
-    float* __restrict__ partial, int H, int W, int CT, int TW, int tw_shift, int tiles_w, int tiles_h, int ntiles) {
+    float* __restrict__ partial, int H, int W, int CT, int CWT, int TW, int tw_shift, int tiles_w, int tiles_h,
+    int ntiles) {
   constexpr int CW = NJ * 32;
   constexpr int MAXT = 408;                     // (TH+2)*(TW+4) cells for every TW in {16,32,64}
   constexpr int SW = CW + 8;                    // row stride of the staged pooled outputs
@@ -571,24 +573,25 @@ __global__ __launch_bounds__(NT, PASS == 3 ? 2 : 1) void k_thin_first(
   const int Hq = H >> 1, Wq = W >> 1;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int frag_row = lane & 31, g = lane >> 5, col_lane = lane & 31;
+  const int c0 = blockIdx.y * CW;               // this workgroup's CW of the layer's CWT wide channels
 
   t_bf16x8 bfrag[3][NJ];
 #pragma unroll
   for (int r = 0; r < 3; ++r)
 #pragma unroll
     for (int j = 0; j < NJ; ++j)
-      bfrag[r][j] = *reinterpret_cast<const t_bf16x8*>(&wfrag[((j * 32 + frag_row) * 3 + r) * 16 + g * 8]);
+      bfrag[r][j] = *reinterpret_cast<const t_bf16x8*>(&wfrag[((c0 + j * 32 + frag_row) * 3 + r) * 16 + g * 8]);
   float bs[NJ], sc[NJ], sh[NJ], mu[NJ], is[NJ], al[NJ], be[NJ], s1[NJ], s2[NJ];
 #pragma unroll
   for (int j = 0; j < NJ; ++j) {
-    const int c = j * 32 + col_lane;
+    const int c = c0 + j * 32 + col_lane;
     bs[j] = bias ? bias[c] : 0.0f;
     sc[j] = (PASS >= 1 && PASS <= 3) ? bn_vec[c] : 1.0f;
-    sh[j] = (PASS >= 1 && PASS <= 3) ? bn_vec[CW + c] : 0.0f;
-    mu[j] = (PASS == 2 || PASS == 3) ? bn_vec[2 * CW + c] : 0.0f;
-    is[j] = (PASS == 2 || PASS == 3) ? bn_vec[3 * CW + c] : 1.0f;
-    const float c1 = PASS == 3 ? bn_vec[4 * CW + c] : 0.0f;
-    const float c2 = PASS == 3 ? bn_vec[5 * CW + c] : 0.0f;
+    sh[j] = (PASS >= 1 && PASS <= 3) ? bn_vec[CWT + c] : 0.0f;
+    mu[j] = (PASS == 2 || PASS == 3) ? bn_vec[2 * CWT + c] : 0.0f;
+    is[j] = (PASS == 2 || PASS == 3) ? bn_vec[3 * CWT + c] : 1.0f;
+    const float c1 = PASS == 3 ? bn_vec[4 * CWT + c] : 0.0f;
+    const float c2 = PASS == 3 ? bn_vec[5 * CWT + c] : 0.0f;
     al[j] = -(sc[j] * c2) * is[j];
     be[j] = sc[j] * (c2 * is[j] * mu[j] - c1);
     s1[j] = 0.0f; s2[j] = 0.0f;
@@ -622,7 +625,7 @@ __global__ __launch_bounds__(NT, PASS == 3 ? 2 : 1) void k_thin_first(
       auto chunk = [&](int i) {
         const int G = wave * 16 + i * 8 + min(lane, 8 * CPR - 1) / CPR, ch = lane % CPR;
         const int hq = (h0 >> 1) + (G >> (tw_shift - 1)), wq = (w0 >> 1) + (G & ((TW >> 1) - 1));
-        return *reinterpret_cast<const uint4*>(dout + (((int64_t)n * Hq + hq) * Wq + wq) * CW + ch * 8);
+        return *reinterpret_cast<const uint4*>(dout + (((int64_t)n * Hq + hq) * Wq + wq) * CWT + c0 + ch * 8);
       };
       gv0 = chunk(0);
       gv1 = chunk(1);
@@ -630,7 +633,7 @@ __global__ __launch_bounds__(NT, PASS == 3 ? 2 : 1) void k_thin_first(
       auto chunk = [&](int idx) {
         const int G = idx / CPR, ch = idx % CPR;
         const int hq = (h0 >> 1) + (G >> (tw_shift - 1)), wq = (w0 >> 1) + (G & ((TW >> 1) - 1));
-        return *reinterpret_cast<const uint4*>(dout + (((int64_t)n * Hq + hq) * Wq + wq) * CW + ch * 8);
+        return *reinterpret_cast<const uint4*>(dout + (((int64_t)n * Hq + hq) * Wq + wq) * CWT + c0 + ch * 8);
       };
       gv0 = chunk(min(tid, GCH - 1));
       if (GPT == 2) gv1 = chunk(min(NT + tid, GCH - 1));
@@ -732,7 +735,7 @@ __global__ __launch_bounds__(NT, PASS == 3 ? 2 : 1) void k_thin_first(
       }
       if (PASS == 4) {
         // ReLU backward of the layer below while storing: its saved activation decides, column sums for its bias
-        bf16_t* out_n = out + (int64_t)n * Hq * Wq * CW;
+        bf16_t* out_n = out + (int64_t)n * Hq * Wq * CWT + c0;
         if (lane < 8 * CPR) {
           const int g8 = lane / CPR, ch = lane % CPR;
           const int G = wave * 16 + i * 8 + g8;
@@ -749,11 +752,11 @@ __global__ __launch_bounds__(NT, PASS == 3 ? 2 : 1) void k_thin_first(
             cs[2 * q + 1] += __uint_as_float(hi);
             ow[q] = lo | hi;
           }
-          *reinterpret_cast<uint4*>(out_n + ((int64_t)hq * Wq + wq) * CW + ch * 8) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+          *reinterpret_cast<uint4*>(out_n + ((int64_t)hq * Wq + wq) * CWT + ch * 8) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
         }
       }
       if (PASS == 1) {
-        bf16_t* out_n = out + (int64_t)n * Hq * Wq * CW;
+        bf16_t* out_n = out + (int64_t)n * Hq * Wq * CWT + c0;
 #pragma unroll
         for (int c = 0; c < (8 * CPR + 63) / 64; ++c) {
           const int idx = c * 64 + lane;
@@ -761,7 +764,7 @@ __global__ __launch_bounds__(NT, PASS == 3 ? 2 : 1) void k_thin_first(
           const int G = wave * 16 + i * 8 + g8;
           const int hq = (h0 >> 1) + (G >> (tw_shift - 1)), wq = (w0 >> 1) + (G & ((TW >> 1) - 1));
           if (idx < 8 * CPR)
-            *reinterpret_cast<uint4*>(out_n + ((int64_t)hq * Wq + wq) * CW + ch * 8) =
+            *reinterpret_cast<uint4*>(out_n + ((int64_t)hq * Wq + wq) * CWT + ch * 8) =
                 *reinterpret_cast<const uint4*>(&stage[g8 * SW + ch * 8]);
         }
       }
@@ -814,7 +817,7 @@ __global__ __launch_bounds__(NT, PASS == 3 ? 2 : 1) void k_thin_first(
     }
     __syncthreads();
     for (int i = tid; i < 2 * CW; i += NT)
-      partial[(int64_t)blockIdx.x * 2 * CW + i] = (sRed[i] + sRed[2 * CW + i]) + (sRed[4 * CW + i] + sRed[6 * CW + i]);
+      partial[((int64_t)blockIdx.x * 2 + i / CW) * CWT + c0 + i % CW] = (sRed[i] + sRed[2 * CW + i]) + (sRed[4 * CW + i] + sRed[6 * CW + i]);
   }
   if (PASS == 3) {
     // sum the four waves in a fixed order through LDS (reusing the slab), then write [cw][64]
@@ -835,7 +838,7 @@ __global__ __launch_bounds__(NT, PASS == 3 ? 2 : 1) void k_thin_first(
       }
     }
     __syncthreads();
-    for (int i = tid; i < CW * 64; i += NT) partial[(int64_t)blockIdx.x * CW * 64 + i] = sF[i];
+    for (int i = tid; i < CW * 64; i += NT) partial[((int64_t)blockIdx.x * CWT + c0) * 64 + i] = sF[i];
   }
 }
 
@@ -1014,19 +1017,20 @@ int launch_thin_in_mfma(const void* thin, const float* wcanon, void* wfrag, cons
 }
 
 // First layer + batch-norm + ReLU + 2x2 max-pool with the convolution output recomputed in every
-// pass (k_thin_first).  Whole patches only, 32 or 64 output channels.
+// pass (k_thin_first).  Whole patches only; 32, 64 or 128 output channels.
 bool thin_first_supported(int ct, int cw, int k, int up, int dtype, int h, int w) {
-  if (!thin_in_mfma_supported(ct, cw, k, up, dtype) || cw > 64 || w % 8 != 0) return false;
+  if (!thin_in_mfma_supported(ct, cw, k, up, dtype) || (cw != 32 && cw != 64 && cw != 128) || w % 8 != 0) return false;
   const ThinTile t = thin_tile(1, h, w);
   return t.tw >= 16 && h % t.th == 0 && w % t.tw == 0;
 }
 
 // workgroups of a pass (each walks the same number of patches when the patch count is a multiple)
-static int thin_first_grid(int tiles, int pass) {
-  const int cap = pass >= 2 ? 512 : 768;        // resident workgroups: registers allow two (passes 2, 3) or three per compute unit
+static int thin_first_grid(int tiles, int cw, int pass) {
+  // resident workgroups: registers allow two (passes 2, 3) or three per compute unit; 128 channels take two workgroup columns
+  const int cap = (pass == 2 || pass == 3 ? 512 : 768) / (cw == 128 ? 2 : 1);
   return tiles < cap ? tiles : cap;
 }
-int thin_first_blocks(int n, int h, int w, int pass) { return thin_first_grid(thin_tile(n, h, w).blocks, pass); }
+int thin_first_blocks(int n, int h, int w, int cw, int pass) { return thin_first_grid(thin_tile(n, h, w).blocks, cw, pass); }
 
 // pass 0: partial <- column statistics (packs wfrag from wcanon first);  pass 1: out <- pooled activation;
 // pass 2: partial <- batch-norm backward sums from the pooled gradient dout;
@@ -1041,17 +1045,18 @@ int launch_thin_first(int pass, const void* thin, const float* wcanon, void* wfr
     return fail(AE_EINVAL, "thin_first: shape not supported");
   if (((uintptr_t)thin & 15) != 0) return fail(AE_EINVAL, "thin_first: input must be 16-byte aligned");
   const ThinTile t = thin_tile(n, h, w);
-  const int nj = cw / 32;
+  const int nj = cw == 32 ? 1 : 2;               // 32-channel column tiles per workgroup; 128 channels: two workgroup columns
+  const int halves = cw / (nj * 32);
   if (wcanon) {
-    hipLaunchKernelGGL(k_thin_pack_wfrag, dim3((unsigned)((nj * 32 * 48 + NT - 1) / NT)), dim3(NT), 0, s, wcanon,
-                       (bf16_t*)wfrag, ct, cw, nj * 32, pass == 4 ? 1 : 0);
+    hipLaunchKernelGGL(k_thin_pack_wfrag, dim3((unsigned)((cw * 48 + NT - 1) / NT)), dim3(NT), 0, s, wcanon,
+                       (bf16_t*)wfrag, ct, cw, cw, pass == 4 ? 1 : 0);
     AE_TRY(launch_status("thin_pack_wfrag"));
   }
-  const int grid = thin_first_grid(t.blocks, pass);
+  const int grid = thin_first_grid(t.blocks, cw, pass);
 #define LAUNCH_TF(NJV, PASSV)                                                                                      \
-  hipLaunchKernelGGL((k_thin_first<NJV, PASSV>), dim3((unsigned)grid), dim3(NT), 0, s, (const bf16_t*)thin,          \
-                     (const bf16_t*)wfrag, bias, bn_vec, (const bf16_t*)dout, (bf16_t*)out, partial, h, w, ct, t.tw, \
-                     t.shift, t.tiles_w, t.tiles_h, t.blocks)
+  hipLaunchKernelGGL((k_thin_first<NJV, PASSV>), dim3((unsigned)grid, (unsigned)halves), dim3(NT), 0, s,             \
+                     (const bf16_t*)thin, (const bf16_t*)wfrag, bias, bn_vec, (const bf16_t*)dout, (bf16_t*)out,     \
+                     partial, h, w, ct, cw, t.tw, t.shift, t.tiles_w, t.tiles_h, t.blocks)
 #define LAUNCH_TF_NJ(PASSV) \
   if (nj == 1) LAUNCH_TF(1, PASSV); else LAUNCH_TF(2, PASSV)
   switch (pass) {

@@ -227,7 +227,7 @@ int launch_thin_in_mfma(const void* thin, const float* wcanon, void* wfrag, cons
                         int n, int h, int w, int ct, int cw, int flip, int act, int upsum, hipStream_t s);
 // first layer + batch-norm + ReLU + pool2 with the convolution output recomputed in every pass
 bool thin_first_supported(int ct, int cw, int k, int up, int dtype, int h, int w);
-int thin_first_blocks(int n, int h, int w, int pass);   // = partial blocks pass 0 / 2 write
+int thin_first_blocks(int n, int h, int w, int cw, int pass);   // = partial blocks pass 0 / 2 write
 int launch_thin_first(int pass, const void* thin, const float* wcanon, void* wfrag, const float* bias,
                       const float* bn_vec, const void* dout, void* out, float* partial, float* dw_canonical, int n, int h,
                       int w, int ct, int cw, hipStream_t s);

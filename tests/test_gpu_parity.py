@@ -243,6 +243,8 @@ FIRST_LAYER_RECOMPUTED = [
     ("in:1x32x32,conv3:64,bn,relu,pool2,conv3:32,bn,relu,pool2,conv1:8,pnorm,awgn,conv1:32,up2,conv3:32,relu,up2,conv3:1,sigmoid", 3),
     ("in:4x8x128,conv3:64,bn,relu,pool2,conv3:32,relu,up2,conv3:4,sigmoid", 2),
     ("in:2x64x64,conv3:32,bn,relu,pool2,conv3:32,relu,up2,conv3:2,sigmoid", 9),
+    # 128 channels on the wide side (two workgroup columns), first and last layer
+    ("in:3x32x32,conv3:128,bn,relu,pool2,conv3:128,relu,up2,conv3:3,sigmoid", 7),
 ]
 
 
@@ -290,6 +292,8 @@ def test_first_layer_conv_output_recomputed_not_stored(ae, case, bn_mode):
     ent, _, _, _ = wl.param_layout(spec, bn_mode)
     first = max(e["offset"] + int(np.prod(e["shape"])) for e in ent if e["op"] <= 1)
     assert first > 9 * 32 and np.array_equal(res[0][3][:first], res[2][3][:first])
+    if case == 4:                                          # no layer of this one takes the fallback kernel
+        assert np.array_equal(res[0][3], res[2][3])
     assert np.array_equal(res[0][2], res[1][2])            # the convolution output itself: same bits either way
     assert_close(res[0][1], res[1][1], 4e-3, "pooled activation, recomputed against stored", tol_max=8e-3)
     assert_close(res[0][0], res[1][0], 1e-2, "y, recomputed against stored", tol_max=3e-2)
