@@ -74,6 +74,8 @@ struct IgemmParams {
   // of the image (Wt = Wc / strips, TH = 256 / Wt); GEMM row m = tile * 256 + th * Wt + tw then is pixel
   // (row block * TH + th, strip * Wt + tw) of its image.  1: a tile spans the image width and rows are pixels in order.
   int strips = 1;
+  int log_wt = 6;              // log2 of the strip width Wc / strips
+  int log_w = -1, log_h = -1;  // log2 of Wc and Hc when both are powers of two (the four-phase output mapping), else -1
   // Companion tensor of the output's shape and layout (interior tiles only): the saved activation a of the layer whose
   // output gradient this launch computes.  With dyv = (a > 0 ? value : 0) per stored value:
   //   1: dyv is stored instead of the value (ReLU backward); partial receives per-tile column sums of dyv (the bias gradient);
@@ -85,21 +87,32 @@ struct IgemmParams {
   const float* comp_bn = nullptr;
 };
 
-// output row (pixel index in y) of GEMM row m
-__device__ __forceinline__ int64_t igemm_out_row(const IgemmParams& p, int64_t m, int phase) {
+// output row (pixel index in y) of GEMM row m.  Column strips: the part that depends on the 256-row tile alone
+// (image, row block, strip) is igemm_strip_base, taken once per tile by the caller; the strip width is a power of two.
+__device__ __forceinline__ int64_t igemm_strip_base(const IgemmParams& p, int64_t m_tile) {
+  const unsigned tile = (unsigned)(m_tile >> 8), wt = 1u << p.log_wt, th_n = 256u >> p.log_wt;
+  const unsigned strip = tile % (unsigned)p.strips, t2 = tile / (unsigned)p.strips;
+  const unsigned blocks = (unsigned)p.Hc / th_n;
+  const unsigned rb = t2 % blocks, img = t2 / blocks;
+  return ((int64_t)img * p.Hc + rb * th_n) * p.Wc + strip * wt;
+}
+__device__ __forceinline__ int64_t igemm_out_row(const IgemmParams& p, int64_t m, int phase, int64_t strip_base) {
   if (p.strips > 1) {
-    const unsigned mu = (unsigned)m, wt = (unsigned)(p.Wc / p.strips), th_n = 256u / wt;
-    const unsigned ml = mu & 255u, tile = mu >> 8;
-    const unsigned tw = ml % wt, th = ml / wt;
-    const unsigned strip = tile % (unsigned)p.strips, t2 = tile / (unsigned)p.strips;
-    const unsigned blocks = (unsigned)p.Hc / th_n;
-    const unsigned rb = t2 % blocks, img = t2 / blocks;
-    return ((int64_t)img * p.Hc + rb * th_n + th) * p.Wc + strip * wt + tw;
+    const unsigned ml = (unsigned)m & 255u;
+    return strip_base + (int64_t)((ml >> p.log_wt) * (unsigned)p.Wc + (ml & ((1u << p.log_wt) - 1u)));
   }
   if (p.phases == 1) return m;
   const unsigned mu = (unsigned)m;
-  const unsigned j = mu % (unsigned)p.Wc, t = mu / (unsigned)p.Wc;
-  const unsigned i = t % (unsigned)p.Hc, n = t / (unsigned)p.Hc;
+  unsigned j, i, n;
+  if (p.log_w >= 0) {        // power-of-two images: no divisions
+    j = mu & ((unsigned)p.Wc - 1u);
+    const unsigned t = mu >> p.log_w;
+    i = t & ((unsigned)p.Hc - 1u); n = t >> p.log_h;
+  } else {
+    j = mu % (unsigned)p.Wc;
+    const unsigned t = mu / (unsigned)p.Wc;
+    i = t % (unsigned)p.Hc; n = t / (unsigned)p.Hc;
+  }
   return ((int64_t)n * (2 * p.Hc) + 2 * i + (phase >> 1)) * (2 * p.Wc) + 2 * j + (phase & 1);
 }
 
@@ -178,6 +191,7 @@ __device__ __forceinline__ void igemm_store_interior(const floatx16 (&acc)[MI][N
   constexpr int EPC = 16 / ES;               // elements per 16-byte chunk
   constexpr int CPRO = WN / EPC;             // chunks per staged row
   const int col_lane = lane & 31, row_lane = (lane >> 5) * 4;
+  const int64_t sbase = p.strips > 1 ? igemm_strip_base(p, mrow0) : 0;   // (a wave's rows lie in one 256-row tile)
   // companion tensor: all of this wave's chunks are requested before the first row is staged, so that their
   // latency runs behind the conversion and the stores of the rows before them
   constexpr int NCH = (32 * CPRO) / 64;
@@ -190,7 +204,7 @@ __device__ __forceinline__ void igemm_store_interior(const floatx16 (&acc)[MI][N
         const int idx = c * 64 + lane;
         const int lr = idx / CPRO, ch = idx % CPRO;
         const T* dst = (p.phases == 1 && p.strips == 1) ? yrow + (int64_t)(i * 32 + lr) * N + ch * EPC
-                                                        : ycol + igemm_out_row(p, mrow0 + i * 32 + lr, phase) * N + ch * EPC;
+                                                        : ycol + igemm_out_row(p, mrow0 + i * 32 + lr, phase, sbase) * N + ch * EPC;
         cmp[i][c] = *reinterpret_cast<const uint4v*>(reinterpret_cast<const T*>(p.comp) + (dst - reinterpret_cast<T*>(p.y)));
       }
   }
@@ -217,7 +231,7 @@ __device__ __forceinline__ void igemm_store_interior(const floatx16 (&acc)[MI][N
       const int idx = c * 64 + lane;
       const int lr = idx / CPRO, ch = idx % CPRO;
       T* dst = (p.phases == 1 && p.strips == 1) ? yrow + (int64_t)(i * 32 + lr) * N + ch * EPC
-                                                : ycol + igemm_out_row(p, mrow0 + i * 32 + lr, phase) * N + ch * EPC;
+                                                : ycol + igemm_out_row(p, mrow0 + i * 32 + lr, phase, sbase) * N + ch * EPC;
       if constexpr (MXQ) {
         // MX block quantisation of the stored row: a block of mx_block columns is mx_block/EPC neighbouring lanes of this
         // pass (a staged row is CPRO >= mx_block/EPC consecutive lanes, blocks do not straddle rows)
@@ -1041,10 +1055,8 @@ static bool conv3_patch_usable(const ConvArgs& a) {
   // (a 128-pixel-wide tile would need 96 KB of LDS, one workgroup per compute unit: wider images are cut into column
   // strips of 64 pixels instead, whose halo columns come from the neighbouring strip)
   if (a.wc != 16 && a.wc != 32 && a.wc != 64 && a.wc != 128 && a.wc != 256) return false;
-  // (measured on the 128 x 128 layers of the largest workload: with four channel slabs the strip form beats the per-tap
-  // kernel, 98 against 109 us; with two slabs the patch of the second slab is all there is to prefetch behind the
-  // first, and the per-tap kernel wins, 111 against 135 us)
-  if (a.wc > 64 && a.cin * (int)dtype_size(a.dtype) < 256) return false;
+  // (measured on the 128 x 128 layers of the largest workload against the per-tap kernel: 93 against 109 us with four
+  // channel slabs, 109 against 131 us with two)
   const int th = 256 / (a.wc > 64 ? 64 : a.wc);
   if (a.hc % th != 0 || a.cout % 64 != 0) return false;
   const int bn = a.cout % 128 == 0 ? 128 : 64;
@@ -1148,6 +1160,11 @@ int launch_conv_mfma(const ConvArgs& a0, hipStream_t s) {
   p.N = a.cout; p.K = a.k * a.k * a.cin;
   p.Hc = a.hc; p.Wc = a.wc; p.Cin = a.cin; p.ksz = a.k; p.up = a.up; p.act = a.act;
   p.Hv = a.hc; p.Wv = a.wc; p.stride = 1; p.pad = (a.k - 1) >> 1; p.phases = 1;
+  if ((a.hc & (a.hc - 1)) == 0 && (a.wc & (a.wc - 1)) == 0) {
+    p.log_w = p.log_h = 0;
+    while ((1 << p.log_w) < a.wc) ++p.log_w;
+    while ((1 << p.log_h) < a.hc) ++p.log_h;
+  }
   p.resid = a0.resid;
   p.comp = a0.comp; p.comp_mode = a0.comp_mode; p.comp_bn = a0.comp_bn;
   if (a0.comp_mode != 0) {
@@ -1179,6 +1196,7 @@ int launch_conv_mfma(const ConvArgs& a0, hipStream_t s) {
     const int bn = a.cout % 128 == 0 ? 128 : 64;
     p.tiles_n = a.cout / bn;
     p.strips = a.wc > 64 ? a.wc / 64 : 1;
+    p.log_wt = 6;                                // strips of 64 pixels
     dim3 pgrid((unsigned)((p.M / 256) * p.tiles_n));
 #define PATCH_LAUNCH_E(T, WV, E)                                                                             \
   do {                                                                                                      \
