@@ -42,9 +42,9 @@ __device__ __forceinline__ void thin_fill_patch(bf16_t* __restrict__ tile, const
   const int tid = threadIdx.x;
   const int64_t HW = (int64_t)H * W;
   if (vec) {
-    const int cpr = IW >> 3;
+    const int cpr = IW >> 3, cshift = 31 - __clz(cpr);   // IW is a power of two
     for (int idx = tid; idx < rows * cpr; idx += NT) {
-      const int pr = idx / cpr, c = idx - pr * cpr;
+      const int pr = idx >> cshift, c = idx & (cpr - 1);
       const int hh = h_first + pr, ww = w_first + 8 * c;
       const bool ok = hh >= 0 && hh < H && ww < W;
       const int64_t off = (int64_t)min(max(hh, 0), H - 1) * W + min(ww, W - 8);
@@ -463,9 +463,9 @@ __device__ __forceinline__ void thin_patch_load(ThinPatchRegs& R, const bf16_t* 
                                                 int h_first, int w_first, int rows, int IW) {
   const int tid = threadIdx.x;
   const int64_t HW = (int64_t)H * W;
-  const int cpr = IW >> 3;
+  const int cpr = IW >> 3, cshift = 31 - __clz(cpr);      // IW is a power of two: no divisions
   if (tid < rows * cpr) {
-    const int pr = tid / cpr, c = tid - pr * cpr;
+    const int pr = tid >> cshift, c = tid & (cpr - 1);
     const int hh = h_first + pr, ww = w_first + 8 * c;
     const int64_t off = (int64_t)min(max(hh, 0), H - 1) * W + min(ww, W - 8);
 #pragma unroll
@@ -485,9 +485,9 @@ __device__ __forceinline__ void thin_patch_store(const ThinPatchRegs& R, bf16_t*
                                                  int h_first, int w_first, int rows, int IW) {
   const int PW = IW + 4;
   const int tid = threadIdx.x;
-  const int cpr = IW >> 3;
+  const int cpr = IW >> 3, cshift = 31 - __clz(cpr);
   if (tid < rows * cpr) {
-    const int pr = tid / cpr, c = tid - pr * cpr;
+    const int pr = tid >> cshift, c = tid & (cpr - 1);
     const int hh = h_first + pr, ww = w_first + 8 * c;
     const bool ok = hh >= 0 && hh < H && ww < W;
     uint32_t v[4][4];
@@ -685,7 +685,7 @@ __global__ __launch_bounds__(NT, PASS == 3 ? 2 : 1) void k_thin_first(
         for (int eg = 0; eg < 4; ++eg) {
           float x[4];                            // the window's conv outputs before rounding
 #pragma unroll
-          for (int k = 0; k < 4; ++k) x[k] = acc[i][j][4 * eg + k] + bs[j];
+          for (int k = 0; k < 4; ++k) x[k] = acc[i][j][4 * eg + k] + ((PASS == 1 || PASS == 2) ? 0.0f : bs[j]);
           if (PASS == 0) {
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
@@ -697,9 +697,10 @@ __global__ __launch_bounds__(NT, PASS == 3 ? 2 : 1) void k_thin_first(
             // input gradient through the x2 upsample: the sum over the 2x2 group (k_thin_in_mfma with UPSUM)
             stage[(eg * 2 + g) * SW + j * 32 + col_lane] = f32_to_bf16((x[0] + x[1]) + (x[2] + x[3]));
           } else if (PASS <= 2) {
+            // (adding the bias is monotonic too: it is added to the selected accumulator only)
             const float hi = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
             const float lo = fminf(fminf(x[0], x[1]), fminf(x[2], x[3]));
-            const float xw = bf16_to_f32(f32_to_bf16(sc[j] > 0.0f ? hi : (sc[j] < 0.0f ? lo : x[0])));
+            const float xw = bf16_to_f32(f32_to_bf16((sc[j] > 0.0f ? hi : (sc[j] < 0.0f ? lo : x[0])) + bs[j]));
             const float pre_w = fmaf(sc[j], xw, sh[j]);
             if (PASS == 1) {
               stage[(eg * 2 + g) * SW + j * 32 + col_lane] = f32_to_bf16(apply_act(pre_w, ACT_RELU));
