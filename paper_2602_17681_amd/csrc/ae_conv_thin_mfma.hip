@@ -940,21 +940,21 @@ __global__ __launch_bounds__(NT) void k_thin_out_mfma(const bf16_t* __restrict__
   const int OW = TW << up, OH = TH << up;
   const int ow_shift = tw_shift + up;
   const int64_t HWc = (int64_t)Hc * Wc;
-  for (int item = tid; item < CT * OH * OW; item += NT) {
+  // (a tap that falls outside the image reads a halo cell, whose Z row is zero because its input was loaded as
+  // zeros: no per-tap bounds checks; -1 >> 1 = -1 addresses the halo as well)
+  const int oh_shift = 8 - tw_shift + up;       // OH = (256 / TW) << up
+#pragma unroll 2
+  for (int item = tid; item < (CT << (oh_shift + ow_shift)); item += NT) {
     const int xl = item & (OW - 1), rr = item >> ow_shift;
-    const int yl = rr & (OH - 1), ct = rr / OH;
+    const int yl = rr & (OH - 1), ct = rr >> oh_shift;
     const int y = (h0 << up) + yl, x = (w0 << up) + xl;
     if (y < Hc && x < Wc) {
       float v = bias ? bias[ct] : 0.0f;
 #pragma unroll
       for (int r = 0; r < 3; ++r) {
-        const int yy = y + r - 1;
-        const int prow = ((yy >> up) - (h0 - 1)) * PW;
+        const int prow = (((y + r - 1) >> up) - (h0 - 1)) * PW;
 #pragma unroll
-        for (int s_ = 0; s_ < 3; ++s_) {
-          const int xx = x + s_ - 1;
-          if (yy >= 0 && yy < Hc && xx >= 0 && xx < Wc) v += sZ[(prow + (xx >> up) - (w0 - 1)) * ZS + (r * 3 + s_) * CT + ct];
-        }
+        for (int s_ = 0; s_ < 3; ++s_) v += sZ[(prow + ((x + s_ - 1) >> up) - (w0 - 1)) * ZS + (r * 3 + s_) * CT + ct];
       }
       const float a = apply_act(bf16_to_f32(f32_to_bf16(v)), act);
       const int64_t o = ((int64_t)n * CT + ct) * HWc + (int64_t)y * Wc + x;
