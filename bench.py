@@ -23,7 +23,12 @@ HBM_PEAK_GBS = 8000.0
 # summarised in the named file under profiles/ (each counter scaled by what it reads for a plain 256 MiB copy: fetch
 # x2.000, write x1.000).  A figure belongs to the kernels as they were when its profile was taken: an entry is removed
 # (traffic = null in the JSON line) when the kernels of its family change, until the counters are collected again.
-TRAFFIC = {}
+TRAFFIC = {
+    # workload -> kernel family -> measured HBM bytes per launch
+    "cfg5": {"k_igemm": {"bytes_per_launch": 93.3e6,
+                         "source": "profiles/cfg5_hbm_traffic.md (kernels as of commit 3af60f6; 20 launches per step, "
+                                   "59.4 MB fetched + 33.8 MB written each)"}},
+}
 
 
 def build_case(name, torch, ae, batch=None):
