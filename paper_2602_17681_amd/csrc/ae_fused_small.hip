@@ -110,6 +110,52 @@ __device__ __forceinline__ void conv3_pixel(const float* src, const float* wl, i
   }
 }
 
+// The 2x2 block of output pixels (rows 2*by, 2*by + 1, columns 2*bx, 2*bx + 1) of a 3x3 convolution behind a x2
+// nearest upsample of src[cin][hs][ws]: the block's 36 taps read only the 3x3 source cells around (by, bx), which
+// are loaded once per input channel, and a weight serves four pixels.  (One pixel per thread, conv3_pixel, is bound
+// by the LDS reads: a value and NCO weights per NCO multiply-adds.)  Each output adds its taps in the order
+// (ci, r, s): the sums are those of conv3_pixel<NCO, true> bit for bit.
+// wl: [ci*9 + tap][wstride], this thread's NCO channels first.  acc[2*a + b] is pixel (2*by + a, 2*bx + b).
+template <int NCO>
+__device__ __forceinline__ void conv3_up_block(const float* src, const float* wl, int wstride, int cin, int hs, int ws,
+                                               int by, int bx, float (&acc)[4][NCO]) {
+  int off[9];
+  bool ok[9];
+#pragma unroll
+  for (int q = 0; q < 9; ++q) {
+    const int yy = by + q / 3 - 1, xx = bx + q % 3 - 1;
+    ok[q] = yy >= 0 && yy < hs && xx >= 0 && xx < ws;
+    off[q] = ok[q] ? yy * ws + xx : 0;
+  }
+  const int plane = hs * ws;
+  for (int ci = 0; ci < cin; ++ci) {
+    const float* sp = src + ci * plane;
+    const float* wp = wl + ci * 9 * wstride;
+    float sv[9];
+#pragma unroll
+    for (int q = 0; q < 9; ++q) sv[q] = ok[q] ? sp[off[q]] : 0.0f;
+#pragma unroll
+    for (int t = 0; t < 9; ++t) {
+      float w[NCO];
+      if constexpr (NCO == 4) {
+        const float4 w4 = *reinterpret_cast<const float4*>(wp + t * wstride);
+        w[0] = w4.x; w[1] = w4.y; w[2] = w4.z; w[3] = w4.w;
+      } else {
+#pragma unroll
+        for (int k = 0; k < NCO; ++k) w[k] = wp[t * wstride + k];
+      }
+#pragma unroll
+      for (int ab = 0; ab < 4; ++ab) {
+        // output row 2*by + a under tap row r is upsampled row 2*by + a + r - 1, i.e. source row by + ((a + r - 1) >> 1)
+        const int dy = ((ab >> 1) + t / 3 - 1) >> 1, dx = ((ab & 1) + t % 3 - 1) >> 1;
+        const float v = sv[(dy + 1) * 3 + dx + 1];
+#pragma unroll
+        for (int k = 0; k < NCO; ++k) acc[ab][k] = fmaf(v, w[k], acc[ab][k]);
+      }
+    }
+  }
+}
+
 // canonical conv weights W[co][ci][3][3] -> wl[(ci*9 + tap)*NCO + k] for co = co0 + k (zero beyond cout)
 __device__ __forceinline__ void stage_weights(const float* __restrict__ w, int cout, int cin, int co0, int nco, float* wl) {
   for (int i = threadIdx.x; i < cin * 9 * nco; i += NT) {
@@ -249,7 +295,7 @@ __global__ __launch_bounds__(NT_MAX) void k_small_tail(SmallArgs a) {
   float* scale = lat + a.n;                       // [c2]
   float* shift = scale + a.c2;
   float* red = shift + a.c2;                      // [NT/64 + 1]
-  float* wl = red + NT / 64 + 4;                  // weights of the decoder convs
+  float* wl = reinterpret_cast<float*>((reinterpret_cast<uintptr_t>(red + NT / 64 + 4) + 15) & ~(uintptr_t)15);   // weights of the decoder convs (16-byte aligned: read four at a time)
   const int b = blockIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   bn_vectors(a.part2, a.B, a.c2, 1.0 / ((double)a.B * hw2), a.params + a.b2, a.params + a.bn2, scale, shift, tmp);
@@ -260,11 +306,28 @@ __global__ __launch_bounds__(NT_MAX) void k_small_tail(SmallArgs a) {
   {
     const float* wf = a.params + a.wf1;
     constexpr int RB = 4;                         // rows per wavefront at a time: 4 * RB loads in flight per lane
+    const bool vec = (F & 3) == 0 && (((uintptr_t)wf | (uintptr_t)a2) & 15) == 0;   // rows in 16-byte pieces: four times the bytes in flight
     for (int o0 = wave * RB; o0 < a.n; o0 += NT / 64 * RB) {
       float acc[RB];
 #pragma unroll
       for (int r = 0; r < RB; ++r) acc[r] = 0.0f;
-      for (int i0 = lane; i0 < F; i0 += 64 * 4) {
+      for (int i0 = 4 * lane; vec && i0 < F; i0 += 256 * 4) {
+        float4 wv[RB][4], av[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int i = i0 + 256 * u;
+          av[u] = i < F ? *reinterpret_cast<const float4*>(&a2[i]) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+          for (int r = 0; r < RB; ++r)
+            wv[r][u] = (i < F && o0 + r < a.n) ? *reinterpret_cast<const float4*>(&wf[(int64_t)(o0 + r) * F + i]) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+          for (int r = 0; r < RB; ++r)
+            acc[r] = fmaf(wv[r][u].w, av[u].w, fmaf(wv[r][u].z, av[u].z, fmaf(wv[r][u].y, av[u].y, fmaf(wv[r][u].x, av[u].x, acc[r]))));
+      }
+      for (int i0 = lane; !vec && i0 < F; i0 += 64 * 4) {
         float wv[RB][4], av[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -306,44 +369,89 @@ __global__ __launch_bounds__(NT_MAX) void k_small_tail(SmallArgs a) {
     }
   }
   __syncthreads();
-  // decoder fc: one thread per output, the latent from LDS
+  // decoder fc: one thread per output, the latent from LDS; a row is read in 16-byte pieces where the blob allows
   {
     const float* wf = a.params + a.wf2;
+    const bool vec = (a.n & 3) == 0 && (((uintptr_t)wf | (uintptr_t)lat) & 15) == 0;
     for (int o = threadIdx.x; o < FD; o += NT) {
       const float* row = wf + (int64_t)o * a.n;
       float acc = a.params[a.bf2 + o];
+      if (vec) {
+#pragma unroll 8
+        for (int j = 0; j < a.n; j += 4) {
+          const float4 w4 = *reinterpret_cast<const float4*>(row + j);
+          const float4 l4 = *reinterpret_cast<const float4*>(lat + j);
+          acc = fmaf(w4.w, l4.w, fmaf(w4.z, l4.z, fmaf(w4.y, l4.y, fmaf(w4.x, l4.x, acc))));
+        }
+      } else {
 #pragma unroll 16
-      for (int j = 0; j < a.n; ++j) acc = fmaf(row[j], lat[j], acc);
+        for (int j = 0; j < a.n; ++j) acc = fmaf(row[j], lat[j], acc);
+      }
       dec[o] = acc;
     }
   }
-  // first decoder conv: x2 upsample of dec [cr][h4 x w4], 3x3 to c3 channels at h2 x w2, ReLU, planar into a3
+  // first decoder conv: x2 upsample of dec [cr][h4 x w4], 3x3 to c3 channels at h2 x w2, ReLU, planar into a3.
+  // A thread owns a 2x2 block of output pixels and four channels; the threads of a wavefront share the channels
+  // (their weight reads are broadcasts).
   for (int co0 = 0; co0 < a.c3; co0 += COB) {
     __syncthreads();
     stage_weights(a.params + a.w3, a.c3, a.cr, co0, COB, wl);
     __syncthreads();
-    for (int p = threadIdx.x; p < hw2; p += NT) {
-      float acc[COB];
+    const int groups = (min(COB, a.c3 - co0) + 3) >> 2;
+    for (int item = threadIdx.x; item < hw4 * groups; item += NT) {
+      const int blk = item % hw4, g4 = item / hw4;
+      const int by = blk / w4, bx = blk % w4;
+      float acc[4][4];
 #pragma unroll
-      for (int k = 0; k < COB; ++k) acc[k] = a.params[a.b3 + co0 + k];
-      conv3_pixel<COB, true>(dec, wl, a.cr, h4, w4, p / w2, p % w2, acc);
+      for (int k = 0; k < 4; ++k) {
+        const float bk = co0 + 4 * g4 + k < a.c3 ? a.params[a.b3 + co0 + 4 * g4 + k] : 0.0f;
 #pragma unroll
-      for (int k = 0; k < COB; ++k) a3[(co0 + k) * hw2 + p] = fmaxf(acc[k], 0.0f);
+        for (int ab = 0; ab < 4; ++ab) acc[ab][k] = bk;
+      }
+      conv3_up_block<4>(dec, wl + 4 * g4, COB, a.cr, h4, w4, by, bx, acc);
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+        if (co0 + 4 * g4 + k < a.c3) {
+#pragma unroll
+          for (int ab = 0; ab < 4; ++ab)
+            a3[(co0 + 4 * g4 + k) * hw2 + (2 * by + (ab >> 1)) * w2 + 2 * bx + (ab & 1)] = fmaxf(acc[ab][k], 0.0f);
+        }
     }
   }
-  // last conv: x2 upsample of a3, 3x3 to c4 <= 4 channels at h x w, sigmoid, planar output
-  __syncthreads();
-  stage_weights(a.params + a.w4, a.c4, a.c3, 0, 4, wl);
+  // last conv: x2 upsample of a3, 3x3 to c4 <= 4 channels at h x w, sigmoid, planar output; 2x2 blocks again
   __syncthreads();
   float* yb = a.y + (int64_t)b * a.c4 * hw;
-  for (int p = threadIdx.x; p < hw; p += NT) {
-    float acc[4];
+  if (a.c4 == 1) {                                 // a single output channel: one accumulator per pixel, not four
+    stage_weights(a.params + a.w4, 1, a.c3, 0, 1, wl);
+    __syncthreads();
+    for (int blk = threadIdx.x; blk < hw2; blk += NT) {
+      const int by = blk / w2, bx = blk % w2;
+      float acc[4][1];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) acc[k] = k < a.c4 ? a.params[a.b4 + k] : 0.0f;
-    conv3_pixel<4, true>(a3, wl, a.c3, h2, w2, p / a.w, p % a.w, acc);
+      for (int ab = 0; ab < 4; ++ab) acc[ab][0] = a.params[a.b4];
+      conv3_up_block<1>(a3, wl, 1, a.c3, h2, w2, by, bx, acc);
+#pragma unroll
+      for (int ab = 0; ab < 4; ++ab) yb[(2 * by + (ab >> 1)) * a.w + 2 * bx + (ab & 1)] = apply_act(acc[ab][0], ACT_SIGMOID);
+    }
+    return;
+  }
+  stage_weights(a.params + a.w4, a.c4, a.c3, 0, 4, wl);
+  __syncthreads();
+  for (int blk = threadIdx.x; blk < hw2; blk += NT) {
+    const int by = blk / w2, bx = blk % w2;
+    float acc[4][4];
 #pragma unroll
     for (int k = 0; k < 4; ++k)
-      if (k < a.c4) yb[(int64_t)k * hw + p] = apply_act(acc[k], ACT_SIGMOID);
+#pragma unroll
+      for (int ab = 0; ab < 4; ++ab) acc[ab][k] = k < a.c4 ? a.params[a.b4 + k] : 0.0f;
+    conv3_up_block<4>(a3, wl, 4, a.c3, h2, w2, by, bx, acc);
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      if (k < a.c4) {
+#pragma unroll
+        for (int ab = 0; ab < 4; ++ab)
+          yb[(int64_t)k * hw + (2 * by + (ab >> 1)) * a.w + 2 * bx + (ab & 1)] = apply_act(acc[ab][k], ACT_SIGMOID);
+      }
   }
 }
 
@@ -354,7 +462,7 @@ size_t lds2(const SmallArgs& a) {
 size_t lds3(const SmallArgs& a) {
   const size_t F = (size_t)(a.c2 + a.cr) * (a.h / 4) * (a.w / 4);
   const size_t wmax = (size_t)a.cr * 9 * COB > (size_t)a.c3 * 9 * 4 ? (size_t)a.cr * 9 * COB : (size_t)a.c3 * 9 * 4;
-  return sizeof(float) * (1024 + F + (size_t)a.c3 * (a.h / 2) * (a.w / 2) + a.n + 2 * a.c2 + NT_MAX / 64 + 4 + wmax);
+  return sizeof(float) * (1024 + F + (size_t)a.c3 * (a.h / 2) * (a.w / 2) + a.n + 2 * a.c2 + NT_MAX / 64 + 4 + 4 + wmax);
 }
 
 #undef NT
