@@ -110,6 +110,48 @@ __device__ __forceinline__ void conv3_pixel(const float* src, const float* wl, i
   }
 }
 
+// The 2x2 block of output pixels (rows 2*by, 2*by + 1, columns 2*bx, 2*bx + 1) of a plain 3x3 convolution of
+// src[cin][hs][ws] (hs, ws even): the block's 36 taps read the 4x4 source window around it, loaded once per input
+// channel; a weight serves four pixels.  Each output adds its taps in the order (ci, r, s) as conv3_pixel does.
+// wl: [ci*9 + tap][wstride], this thread's NCO channels first.  acc[2*a + b] is pixel (2*by + a, 2*bx + b).
+template <int NCO>
+__device__ __forceinline__ void conv3_block(const float* src, const float* wl, int wstride, int cin, int hs, int ws,
+                                            int by, int bx, float (&acc)[4][NCO]) {
+  int off[16];
+  bool ok[16];
+#pragma unroll
+  for (int q = 0; q < 16; ++q) {
+    const int yy = 2 * by + q / 4 - 1, xx = 2 * bx + q % 4 - 1;
+    ok[q] = yy >= 0 && yy < hs && xx >= 0 && xx < ws;
+    off[q] = ok[q] ? yy * ws + xx : 0;
+  }
+  const int plane = hs * ws;
+  for (int ci = 0; ci < cin; ++ci) {
+    const float* sp = src + ci * plane;
+    const float* wp = wl + ci * 9 * wstride;
+    float sv[16];
+#pragma unroll
+    for (int q = 0; q < 16; ++q) sv[q] = ok[q] ? sp[off[q]] : 0.0f;
+#pragma unroll
+    for (int t = 0; t < 9; ++t) {
+      float w[NCO];
+      if constexpr (NCO == 4) {
+        const float4 w4 = *reinterpret_cast<const float4*>(wp + t * wstride);
+        w[0] = w4.x; w[1] = w4.y; w[2] = w4.z; w[3] = w4.w;
+      } else {
+#pragma unroll
+        for (int k = 0; k < NCO; ++k) w[k] = wp[t * wstride + k];
+      }
+#pragma unroll
+      for (int ab = 0; ab < 4; ++ab) {
+        const float v = sv[((ab >> 1) + t / 3) * 4 + (ab & 1) + t % 3];
+#pragma unroll
+        for (int k = 0; k < NCO; ++k) acc[ab][k] = fmaf(v, w[k], acc[ab][k]);
+      }
+    }
+  }
+}
+
 // The 2x2 block of output pixels (rows 2*by, 2*by + 1, columns 2*bx, 2*bx + 1) of a 3x3 convolution behind a x2
 // nearest upsample of src[cin][hs][ws]: the block's 36 taps read only the 3x3 source cells around (by, bx), which
 // are loaded once per input channel, and a weight serves four pixels.  (One pixel per thread, conv3_pixel, is bound
@@ -262,24 +304,45 @@ __global__ __launch_bounds__(NT_CONV2) void k_small_conv2(SmallArgs a) {
   bn_relu_pool_to_lds(a.raw1 + (int64_t)b * a.h * a.w * a.c1, a.h, a.w, a.c1, scale, shift, a1);
   __syncthreads();
   const float* bias = a.params + a.b2;
-  float s1[COB], s2[COB];
+  // a thread owns a 2x2 block of output pixels and four of the workgroup's COB channels; the threads of a wavefront
+  // share the channels (their weight reads are broadcasts)
+  const int h4 = h2 / 2, w4 = w2 / 2, nblk = h4 * w4;
+  float* part = red + NT / 64 * 2 * COB;          // [item][sum | sum sq][4]: statistics of each item's 16 outputs
+  for (int item = threadIdx.x; item < nblk * (COB / 4); item += NT) {
+    const int blk = item % nblk, g4 = item / nblk;
+    const int by = blk / w4, bx = blk % w4;
+    float acc[4][4], bk[4];
 #pragma unroll
-  for (int k = 0; k < COB; ++k) { s1[k] = 0.0f; s2[k] = 0.0f; }
-  for (int p = threadIdx.x; p < hw2; p += NT) {
-    float acc[COB];
+    for (int k = 0; k < 4; ++k) {
+      bk[k] = bias[co0 + 4 * g4 + k];
 #pragma unroll
-    for (int k = 0; k < COB; ++k) acc[k] = bias[co0 + k];
-    conv3_pixel<COB, false>(a1, wl, a.c1, h2, w2, p / w2, p % w2, acc);
-    float* dst = a.raw2 + ((int64_t)b * hw2 + p) * a.c2 + co0;
-#pragma unroll
-    for (int k = 0; k < COB; ++k) {
-      dst[k] = acc[k];
-      const float d = acc[k] - bias[co0 + k];
-      s1[k] += d;
-      s2[k] = fmaf(d, d, s2[k]);
+      for (int ab = 0; ab < 4; ++ab) acc[ab][k] = bk[k];
     }
+    conv3_block<4>(a1, wl + 4 * g4, COB, a.c1, h2, w2, by, bx, acc);
+    float s1[4] = {0.f, 0.f, 0.f, 0.f}, s2[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ab = 0; ab < 4; ++ab) {
+      const int pix = (2 * by + (ab >> 1)) * w2 + 2 * bx + (ab & 1);
+      *reinterpret_cast<float4*>(a.raw2 + ((int64_t)b * hw2 + pix) * a.c2 + co0 + 4 * g4) =
+          make_float4(acc[ab][0], acc[ab][1], acc[ab][2], acc[ab][3]);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const float d = acc[ab][k] - bk[k];
+        s1[k] += d;
+        s2[k] = fmaf(d, d, s2[k]);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) { part[item * 8 + k] = s1[k]; part[item * 8 + 4 + k] = s2[k]; }
   }
-  write_stats<COB>(s1, s2, red, a.part2, b, a.c2, co0);
+  __syncthreads();
+  // channel sums over the blocks in index order
+  if ((int)threadIdx.x < 2 * COB) {
+    const int q = threadIdx.x / COB, kk = threadIdx.x % COB;
+    float t = 0.0f;
+    for (int blk = 0; blk < nblk; ++blk) t += part[(blk + nblk * (kk >> 2)) * 8 + q * 4 + (kk & 3)];
+    if (co0 + kk < a.c2) a.part2[((int64_t)b * 2 + q) * a.c2 + co0 + kk] = t;
+  }
 }
 
 // ---- launch 3: everything from the second batch-norm to y ----------------------------------------------------------
@@ -457,7 +520,8 @@ __global__ __launch_bounds__(NT_MAX) void k_small_tail(SmallArgs a) {
 
 size_t lds1(const SmallArgs& a) { return sizeof(float) * ((size_t)a.c0 * a.h * a.w + (size_t)a.c0 * 9 * COB + NT_MAX / 64 * 2 * COB); }
 size_t lds2(const SmallArgs& a) {
-  return sizeof(float) * (1024 + (size_t)a.c1 * (a.h / 2) * (a.w / 2) + (size_t)a.c1 * 9 * COB + 2 * a.c1 + NT_CONV2 / 64 * 2 * COB);
+  return sizeof(float) * (1024 + (size_t)a.c1 * (a.h / 2) * (a.w / 2) + (size_t)a.c1 * 9 * COB + 2 * a.c1 + NT_CONV2 / 64 * 2 * COB +
+                          (size_t)(a.h / 4) * (a.w / 4) * (COB / 4) * 8);
 }
 size_t lds3(const SmallArgs& a) {
   const size_t F = (size_t)(a.c2 + a.cr) * (a.h / 4) * (a.w / 4);
