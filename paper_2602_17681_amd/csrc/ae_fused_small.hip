@@ -207,27 +207,6 @@ __device__ __forceinline__ void stage_weights(const float* __restrict__ w, int c
   }
 }
 
-// per-channel partial statistics of this workgroup's conv outputs, about the bias: s1[k], s2[k] summed over the
-// workgroup's threads (lanes by shuffles, then the four wavefronts in index order) into
-// partial[(b*2 + q)*C + co0 + k]; red: 4 * 2 * NCO floats of LDS
-template <int NCO>
-__device__ __forceinline__ void write_stats(const float (&s1)[NCO], const float (&s2)[NCO], float* red, float* partial, int b,
-                                            int C, int co0) {
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  __syncthreads();
-#pragma unroll
-  for (int k = 0; k < NCO; ++k) {
-    const float t1 = wave_sum(s1[k]), t2 = wave_sum(s2[k]);
-    if (lane == 0) { red[wave * 2 * NCO + k] = t1; red[wave * 2 * NCO + NCO + k] = t2; }
-  }
-  __syncthreads();
-  if ((int)threadIdx.x < 2 * NCO) {
-    const int q = threadIdx.x / NCO, k = threadIdx.x % NCO;
-    float t = 0.0f;
-    for (int w = 0; w < NT / 64; ++w) t += red[w * 2 * NCO + threadIdx.x];
-    if (co0 + k < C) partial[((int64_t)b * 2 + q) * C + co0 + k] = t;
-  }
-}
 
 struct SmallArgs {
   const float* x; const float* params; float* y;
@@ -242,7 +221,7 @@ __global__ __launch_bounds__(NT_MAX) void k_small_conv1(SmallArgs a) {
   extern __shared__ float lds[];
   float* img = lds;                               // [c0][h*w]
   float* wl = img + a.c0 * a.h * a.w;             // [c0*9][COB]
-  float* red = wl + a.c0 * 9 * COB;               // [4][2*COB]
+  float* red = wl + a.c0 * 9 * COB;               // [NT][2*COB + 1]: per-thread statistics (odd stride: no bank conflicts)
   const int b = blockIdx.x, hw = a.h * a.w;
   const float* xb = a.x + (int64_t)b * a.c0 * hw;
   for (int i = threadIdx.x; i < a.c0 * hw; i += NT) img[i] = xb[i];
@@ -259,16 +238,36 @@ __global__ __launch_bounds__(NT_MAX) void k_small_conv1(SmallArgs a) {
 #pragma unroll
       for (int k = 0; k < COB; ++k) acc[k] = bias[co0 + k];
       conv3_pixel<COB, false>(img, wl, a.c0, a.h, a.w, p / a.w, p % a.w, acc);
-      float* dst = a.raw1 + ((int64_t)b * hw + p) * a.c1 + co0;
+      float* dst = a.raw1 + ((int64_t)b * hw + p) * a.c1 + co0;    // (c1 and co0 are multiples of COB: 16-byte pieces)
+#pragma unroll
+      for (int k = 0; k < COB; k += 4) *reinterpret_cast<float4*>(dst + k) = make_float4(acc[k], acc[k + 1], acc[k + 2], acc[k + 3]);
 #pragma unroll
       for (int k = 0; k < COB; ++k) {
-        dst[k] = acc[k];
         const float d = acc[k] - bias[co0 + k];
         s1[k] += d;
         s2[k] = fmaf(d, d, s2[k]);
       }
     }
-    write_stats<COB>(s1, s2, red, a.part1, b, a.c1, co0);
+    // channel sums over the threads in a fixed order, through LDS: groups of 32 threads, then the groups
+    constexpr int SR = 2 * COB + 1;
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < COB; ++k) { red[threadIdx.x * SR + k] = s1[k]; red[threadIdx.x * SR + COB + k] = s2[k]; }
+    __syncthreads();
+    {
+      const int c = threadIdx.x % (2 * COB), g = threadIdx.x / (2 * COB);      // NT / 32 groups of 32 threads
+      float t = 0.0f;
+      for (int th = g * 32; th < g * 32 + 32; ++th) t += red[th * SR + c];
+      __syncthreads();
+      red[g * SR + c] = t;
+      __syncthreads();
+      if (g == 0) {
+        float u = 0.0f;
+        for (int gg = 0; gg < NT / 32; ++gg) u += red[gg * SR + c];
+        const int q = c / COB, k = c % COB;
+        if (co0 + k < a.c1) a.part1[((int64_t)b * 2 + q) * a.c1 + co0 + k] = u;
+      }
+    }
   }
 }
 
@@ -518,7 +517,7 @@ __global__ __launch_bounds__(NT_MAX) void k_small_tail(SmallArgs a) {
   }
 }
 
-size_t lds1(const SmallArgs& a) { return sizeof(float) * ((size_t)a.c0 * a.h * a.w + (size_t)a.c0 * 9 * COB + NT_MAX / 64 * 2 * COB); }
+size_t lds1(const SmallArgs& a) { return sizeof(float) * ((size_t)a.c0 * a.h * a.w + (size_t)a.c0 * 9 * COB + (size_t)NT_MAX * (2 * COB + 1)); }
 size_t lds2(const SmallArgs& a) {
   return sizeof(float) * (1024 + (size_t)a.c1 * (a.h / 2) * (a.w / 2) + (size_t)a.c1 * 9 * COB + 2 * a.c1 + NT_CONV2 / 64 * 2 * COB +
                           (size_t)(a.h / 4) * (a.w / 4) * (COB / 4) * 8);
