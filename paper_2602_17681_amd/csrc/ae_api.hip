@@ -555,8 +555,8 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
     TIMED_ON(ws, si, wgrad_mfma_up_phases(wa) ? "bwd.wgrad_mfma_phases" : "bwd.wgrad_mfma", conv_flops,
              (in_el + raw_el) * es + wel * 4, launch_wgrad_mfma(wa, wws, ws));
   } else {
-    TIMED_ON(ws, si, "bwd.wgrad_zero", 0.0, wel * 4, launch_fill_zero(grads + st.w_off, (int64_t)wel * 4, ws));
-    TIMED_ON(ws, si, "bwd.wgrad_direct", conv_flops, (in_el + raw_el) * es + wel * 4, launch_wgrad_direct(wa, ws));
+    TIMED_ON(ws, si, "bwd.wgrad_direct", conv_flops, (in_el + raw_el) * es + wel * 4,
+             launch_wgrad_direct(wa, wws, wws == m->wgrad_ws ? P.max_wgrad_floats : P.max_wgrad_inorder_floats, ws));
   }
   AE_TRY(wgrad_enqueued());
   // input gradient: convolution of dr with the flipped, transposed weights at conv resolution

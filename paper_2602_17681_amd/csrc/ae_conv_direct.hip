@@ -47,12 +47,14 @@ __global__ void k_conv_direct(const T* __restrict__ x, const T* __restrict__ wp,
   }
 }
 
-// Weight gradient, written in the canonical layout dW[co][ci][r][s] (fp32).
-// grid.x covers the weights (ci fastest so that x reads coalesce), grid.y splits
-// the pixels; partial sums are added with atomics (dW must start at zero).
+// Weight gradient.  grid.x covers the weights (ci fastest so that x reads coalesce), grid.y splits the
+// pixels into chunks; chunk c leaves its sums in partial[c][widx] and k_wgrad_direct_reduce adds the
+// chunks in index order into the canonical layout dW[co][ci][r][s] (fp32): no atomics, the same bits every run.
+// With a single chunk the kernel writes dW itself (partial = null).
 template <typename T>
-__global__ void k_wgrad_direct(const T* __restrict__ x, const T* __restrict__ dy, float* __restrict__ dw, int64_t rows,
-                               int rows_per_block, int Hc, int Wc, int Cin, int Cout, int k, int up) {
+__global__ void k_wgrad_direct(const T* __restrict__ x, const T* __restrict__ dy, float* __restrict__ dw,
+                               float* __restrict__ partial, int64_t rows, int rows_per_block, int Hc, int Wc, int Cin,
+                               int Cout, int k, int up) {
   const int p = (k - 1) >> 1;
   const int Hin = Hc >> up, Win = Wc >> up;
   const int64_t nweights = (int64_t)Cout * k * k * Cin;
@@ -75,7 +77,22 @@ __global__ void k_wgrad_direct(const T* __restrict__ x, const T* __restrict__ dy
     const float xv = Store<T>::ld(x + ((n * Hin + (hh >> up)) * Win + (ww >> up)) * Cin + ci);
     acc = fmaf(Store<T>::ld(dy + m * Cout + co), xv, acc);
   }
-  atomicAdd(dw + (((int64_t)co * Cin + ci) * k + r) * k + s, acc);
+  if (partial) partial[(int64_t)blockIdx.y * nweights + widx] = acc;
+  else dw[(((int64_t)co * Cin + ci) * k + r) * k + s] = acc;
+}
+
+__global__ void k_wgrad_direct_reduce(const float* __restrict__ partial, int chunks, int64_t nweights, int Cin, int k,
+                                      float* __restrict__ dw) {
+  const int64_t widx = (int64_t)blockIdx.x * NT + threadIdx.x;
+  if (widx >= nweights) return;
+  float acc = 0.0f;
+  for (int c = 0; c < chunks; ++c) acc += partial[(int64_t)c * nweights + widx];
+  const int ci = (int)(widx % Cin);
+  int64_t t = widx / Cin;
+  const int s = (int)(t % k); t /= k;
+  const int r = (int)(t % k);
+  const int64_t co = t / k;
+  dw[((co * Cin + ci) * k + r) * k + s] = acc;
 }
 
 }  // namespace
@@ -93,26 +110,49 @@ int launch_conv_direct(const ConvArgs& a, hipStream_t s) {
   return launch_status("conv_direct");
 }
 
-int launch_wgrad_direct(const WgradArgs& a, hipStream_t s) {
+// pixel chunks of the fallback weight gradient: enough to fill the machine, at least 512 rows each, at most 16
+static int64_t wgrad_direct_chunks(const WgradArgs& a) {
   const int64_t rows = (int64_t)a.n * a.hc * a.wc;
   const int64_t nweights = (int64_t)a.cout * a.k * a.k * a.cin;
   const int64_t gx = (nweights + NT - 1) / NT;
-  // enough pixel chunks to fill the machine, at least 512 rows each
   int64_t chunks = (4096 + gx - 1) / gx;
-  int64_t max_chunks = (rows + 511) / 512;
+  const int64_t max_chunks = (rows + 511) / 512;
   if (chunks > max_chunks) chunks = max_chunks;
+  if (chunks > 16) chunks = 16;
+  return chunks < 1 ? 1 : chunks;
+}
+
+// scratch (floats) launch_wgrad_direct wants for its chunk sums; with less it uses fewer chunks
+int64_t wgrad_direct_workspace_floats(const WgradArgs& a) {
+  const int64_t chunks = wgrad_direct_chunks(a);
+  return chunks > 1 ? chunks * a.cout * a.k * a.k * a.cin : 0;
+}
+
+int launch_wgrad_direct(const WgradArgs& a, float* workspace, int64_t workspace_floats, hipStream_t s) {
+  const int64_t rows = (int64_t)a.n * a.hc * a.wc;
+  const int64_t nweights = (int64_t)a.cout * a.k * a.k * a.cin;
+  const int64_t gx = (nweights + NT - 1) / NT;
+  int64_t chunks = wgrad_direct_chunks(a);
+  if (!workspace) workspace_floats = 0;
+  if (chunks * nweights > workspace_floats) chunks = workspace_floats / nweights;
   if (chunks < 1) chunks = 1;
-  if (chunks > 65535) chunks = 65535;
   const int rpb = (int)((rows + chunks - 1) / chunks);
   chunks = (rows + rpb - 1) / rpb;
+  float* partial = chunks > 1 ? workspace : nullptr;
   dim3 grid((unsigned)gx, (unsigned)chunks);
   if (a.dtype == AE_BF16)
     hipLaunchKernelGGL((k_wgrad_direct<bf16_t>), grid, dim3(NT), 0, s, (const bf16_t*)a.x, (const bf16_t*)a.dy,
-                       a.dw_canonical, rows, rpb, a.hc, a.wc, a.cin, a.cout, a.k, a.up);
+                       a.dw_canonical, partial, rows, rpb, a.hc, a.wc, a.cin, a.cout, a.k, a.up);
   else
     hipLaunchKernelGGL((k_wgrad_direct<float>), grid, dim3(NT), 0, s, (const float*)a.x, (const float*)a.dy,
-                       a.dw_canonical, rows, rpb, a.hc, a.wc, a.cin, a.cout, a.k, a.up);
-  return launch_status("wgrad_direct");
+                       a.dw_canonical, partial, rows, rpb, a.hc, a.wc, a.cin, a.cout, a.k, a.up);
+  AE_TRY(launch_status("wgrad_direct"));
+  if (chunks > 1) {
+    hipLaunchKernelGGL(k_wgrad_direct_reduce, dim3((unsigned)gx), dim3(NT), 0, s, partial, (int)chunks, nweights, a.cin, a.k,
+                       a.dw_canonical);
+    return launch_status("wgrad_direct_reduce");
+  }
+  return AE_OK;
 }
 
 }  // namespace ae

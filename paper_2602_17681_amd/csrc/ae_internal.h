@@ -205,7 +205,8 @@ struct WgradArgs {
   const void* x; const void* dy; float* dw_canonical;  // dw is accumulated with atomics: must be zeroed first
   int n, hc, wc, cin, cout, k, up, dtype;
 };
-int launch_wgrad_direct(const WgradArgs& a, hipStream_t s);
+int64_t wgrad_direct_workspace_floats(const WgradArgs& a);   // scratch the fallback weight gradient wants (fewer chunks with less)
+int launch_wgrad_direct(const WgradArgs& a, float* workspace, int64_t workspace_floats, hipStream_t s);
 bool wgrad_mfma_supported(const WgradArgs& a);
 bool wgrad_mfma_up_phases(const WgradArgs& a);   // will it run as the phase form of an upsampled conv (4/9 of the multiply-adds)?
 int64_t wgrad_mfma_workspace_floats(const WgradArgs& a);

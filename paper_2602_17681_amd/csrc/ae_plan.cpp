@@ -324,10 +324,14 @@ int build_plan(const char* spec, int batch, int dtype, int bn_mode, Plan* plan) 
       }
       else if (wgrad_mfma_supported(wa))
         plan->max_wgrad_floats = std::max(plan->max_wgrad_floats, wgrad_mfma_workspace_floats(wa));
+      else
+        plan->max_wgrad_floats = std::max(plan->max_wgrad_floats, wgrad_direct_workspace_floats(wa));
       // a layer without batch-norm, activation or pooling has no conv-output gradient buffer of its own: its
       // weight gradient runs in order on the caller's stream, with scratch apart from the side stream's
-      if (!st.has_bn && !st.pool && st.act == ACT_NONE && st.thin == 0 && wgrad_mfma_supported(wa))
-        plan->max_wgrad_inorder_floats = std::max(plan->max_wgrad_inorder_floats, wgrad_mfma_workspace_floats(wa));
+      if (!st.has_bn && !st.pool && st.act == ACT_NONE && st.thin == 0)
+        plan->max_wgrad_inorder_floats = std::max(plan->max_wgrad_inorder_floats,
+                                                  wgrad_mfma_supported(wa) ? wgrad_mfma_workspace_floats(wa)
+                                                                           : wgrad_direct_workspace_floats(wa));
       if (st.thin == 2)
         plan->max_partial_floats = std::max(plan->max_partial_floats,
                                             B * plane_sums_split((int64_t)st.hc * st.wc) * 2 * (int64_t)st.cout);

@@ -21,5 +21,6 @@ int64_t conv_mfma_splitk_floats(const ConvArgs& a) {
 bool thin_wgrad_mfma_supported(int ct, int cw, int wq, int dtype) { return dtype == 1 && ct <= 4 && cw % 16 == 0 && wq % 16 == 0; }
 int64_t thin_wgrad_workspace_floats(int64_t q_pixels, int ct, int cw) { return (q_pixels / 256 + 1) * 9 * ct * cw; }
 int64_t wgrad_mfma_workspace_floats(const WgradArgs& a) { return (int64_t)8 * a.cout * a.cin * a.k * a.k; }
+int64_t wgrad_direct_workspace_floats(const WgradArgs& a) { return (int64_t)4 * a.cout * a.cin * a.k * a.k; }
 int64_t thin_wgrad_mfma_workspace_floats(int n, int hq, int wq, int cw) { return ((int64_t)n * hq * wq / 1024 + 1) * 9 * 4 * cw; }
 }  // namespace ae

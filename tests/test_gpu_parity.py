@@ -285,15 +285,8 @@ def test_first_layer_conv_output_recomputed_not_stored(ae, case, bn_mode):
         m.model_get_conv_output(0, c0)
         res.append((y.float().cpu().numpy().copy(), a0.cpu().numpy(), c0.cpu().numpy(), g.cpu().numpy()))
     m.close()
-    for k in range(3):                                     # deterministic
-        assert np.array_equal(res[0][k], res[2][k])
-    # ... and so are the first layer's gradients (a later layer of 32 channels takes the generic fallback kernel,
-    # whose weight gradient is accumulated with floating-point atomics)
-    ent, _, _, _ = wl.param_layout(spec, bn_mode)
-    first = max(e["offset"] + int(np.prod(e["shape"])) for e in ent if e["op"] <= 1)
-    assert first > 9 * 32 and np.array_equal(res[0][3][:first], res[2][3][:first])
-    if case == 4:                                          # no layer of this one takes the fallback kernel
-        assert np.array_equal(res[0][3], res[2][3])
+    for k in range(4):                                     # deterministic (the 32-channel layers of these networks
+        assert np.array_equal(res[0][k], res[2][k])        # take the generic fallback kernels: they are, too)
     assert np.array_equal(res[0][2], res[1][2])            # the convolution output itself: same bits either way
     assert_close(res[0][1], res[1][1], 4e-3, "pooled activation, recomputed against stored", tol_max=8e-3)
     assert_close(res[0][0], res[1][0], 1e-2, "y, recomputed against stored", tol_max=3e-2)
