@@ -552,7 +552,7 @@ __device__ __forceinline__ void thin_patch_store(const ThinPatchRegs& R, bf16_t*
 // next patch's global loads in flight while it computes.
 // ---------------------------------------------------------------------------
 template <int NJ, int PASS>
-__global__ __launch_bounds__(NT, PASS == 3 ? 2 : 1) void k_thin_first(
+__global__ __launch_bounds__(NT, (PASS == 3 && NJ == 2) ? 2 : 3) void k_thin_first(
     const bf16_t* __restrict__ thin, const bf16_t* __restrict__ wfrag, const float* __restrict__ bias,
     const float* __restrict__ bn_vec, const bf16_t* __restrict__ dout, bf16_t* __restrict__ out,
     float* __restrict__ partial, int H, int W, int CT, int CWT, int TW, int tw_shift, int tiles_w, int tiles_h,
@@ -1026,9 +1026,12 @@ bool thin_first_supported(int ct, int cw, int k, int up, int dtype, int h, int w
 }
 
 // workgroups of a pass (each walks the same number of patches when the patch count is a multiple)
+// channels per workgroup column: 64, but 32 in pass 3 (its 64-channel form needs 248 registers, two workgroups per
+// compute unit; with 32 channels three fit and the recomputed convolution costs next to nothing)
+static int thin_first_nj(int cw, int pass) { return (cw == 32 || pass == 3) ? 1 : 2; }
 static int thin_first_grid(int tiles, int cw, int pass) {
-  // resident workgroups: registers allow two (passes 2, 3) or three per compute unit; 128 channels take two workgroup columns
-  const int cap = (pass == 2 || pass == 3 ? 512 : 768) / (cw == 128 ? 2 : 1);
+  // resident workgroups: registers allow three per compute unit, shared by the workgroup columns
+  const int cap = 768 / (cw / (32 * thin_first_nj(cw, pass)));
   return tiles < cap ? tiles : cap;
 }
 int thin_first_blocks(int n, int h, int w, int cw, int pass) { return thin_first_grid(thin_tile(n, h, w).blocks, cw, pass); }
@@ -1046,7 +1049,7 @@ int launch_thin_first(int pass, const void* thin, const float* wcanon, void* wfr
     return fail(AE_EINVAL, "thin_first: shape not supported");
   if (((uintptr_t)thin & 15) != 0) return fail(AE_EINVAL, "thin_first: input must be 16-byte aligned");
   const ThinTile t = thin_tile(n, h, w);
-  const int nj = cw == 32 ? 1 : 2;               // 32-channel column tiles per workgroup; 128 channels: two workgroup columns
+  const int nj = thin_first_nj(cw, pass);        // 32-channel column tiles per workgroup; more channels: several workgroup columns
   const int halves = cw / (nj * 32);
   if (wcanon) {
     hipLaunchKernelGGL(k_thin_pack_wfrag, dim3((unsigned)((cw * 48 + NT - 1) / NT)), dim3(NT), 0, s, wcanon,
