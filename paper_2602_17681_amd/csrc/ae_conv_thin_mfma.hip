@@ -543,9 +543,9 @@ __device__ __forceinline__ void thin_patch_store(const ThinPatchRegs& R, bf16_t*
 // relu(scale*x_w + shift) with x_w the rounded maximum of the window for scale > 0, the minimum for
 // scale < 0, x_0 for scale = 0 (all equal: the first wins) — passes 1 and 2 need nothing else of the
 // window, and give the bits of k_post_forward / PostBwdWindow.  Pass 3 finds the winner as the first
-// k whose pre-activation equals the maximum, and evaluates dx_k as alpha*x_k + beta (+ scale*dy at the
-// winner) with alpha = -scale*c2*invstd, beta = scale*(c2*invstd*mean - c1): the formula of
-// k_post_bwd_apply up to binary32 rounding, before the rounding to storage.
+// k whose pre-activation equals the maximum, and evaluates dx_k as alpha*x_k + beta with alpha = -scale*c2*invstd,
+// beta = scale*(c2*invstd*mean - c1), and beta + scale*dy at the winner: the formula of k_post_bwd_apply up to
+// binary32 rounding, before the rounding to storage.
 // Patches are interior (H, W multiples of the patch); a workgroup computes CW = 32*NJ of the layer's CWT wide
 // channels (blockIdx.y selects which: 128 channels run as two halves), the input is 16-byte aligned with
 // W % 8 == 0; a workgroup walks over patches t = blockIdx.x, blockIdx.x + gridDim.x, ... and has the
@@ -721,16 +721,16 @@ __global__ __launch_bounds__(NT, (PASS == 3 && NJ == 2) ? 2 : 3) void k_thin_fir
               pk[k] = fmaf(sc[j], x[k], sh[j]);
             }
             const float pm = fmaxf(fmaxf(pk[0], pk[1]), fmaxf(pk[2], pk[3]));
-            const float sdy = pm > 0.0f ? sc[j] * gg : 0.0f;         // scale*dy at the winner
-            const int arg = pk[0] == pm ? 0 : (pk[1] == pm ? 1 : (pk[2] == pm ? 2 : 3));
+            // the winner (first k whose pre-activation is the maximum) gets beta + scale*dy as its constant term
+            const float bw = be[j] + (pm > 0.0f ? sc[j] * gg : 0.0f);
+            const bool m0 = pk[0] == pm, m1 = pk[1] == pm, m2 = pk[2] == pm;
+            const bool f[4] = {m0, m1 && !m0, m2 && !(m0 || m1), !(m0 || m1 || m2)};
             int th, tw;
             thin_row_pixel<true>(wave * 64 + i * 32 + eg * 8 + g * 4, TW, tw_shift, th, tw);
             bf16_t* dst = &sW[(th * TW + tw) * LA + j * 32 + col_lane];
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-              const float o = fmaf(al[j], x[k], be[j]) + (arg == k ? sdy : 0.0f);
-              dst[((k >> 1) * TW + (k & 1)) * LA] = f32_to_bf16(o);
-            }
+            for (int k = 0; k < 4; ++k)
+              dst[((k >> 1) * TW + (k & 1)) * LA] = f32_to_bf16(fmaf(al[j], x[k], f[k] ? bw : be[j]));
           }
         }
       }
