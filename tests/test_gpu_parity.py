@@ -293,6 +293,28 @@ def test_first_layer_conv_output_recomputed_not_stored(ae, case, bn_mode):
     assert_close(res[0][3], res[1][3], 1e-2, "gradients, recomputed against stored", tol_max=5e-2)
 
 
+def test_changing_the_recompute_setting_between_forward_and_backward_is_refused(ae):
+    """A backward pass needs a forward pass taken with the same setting (the stored-output path keeps a tensor the
+    recomputing one does not): AE_ESTATE, no kernel runs; after a new forward pass it works."""
+    import torch
+    spec, batch = FIRST_LAYER_RECOMPUTED[0]
+    m = ae.Model(spec, batch, ae.AE_BF16)
+    p = torch.from_numpy(wl.make_params(spec, 5, perturb=True, bf16=True)).cuda()
+    x = torch.from_numpy(wl.make_input(spec, batch, 5, bf16=True)).cuda().to(torch.bfloat16)
+    y = torch.empty((batch,) + m.out_shape, dtype=torch.bfloat16, device="cuda")
+    g = torch.zeros(m.n_params, device="cuda")
+    m.model_forward(p, x, 9.0, 5, y)
+    m.model_set_recompute(0)
+    with pytest.raises(ae.AeError) as e:
+        m.model_backward(p, x, torch.ones_like(y), g)
+    assert e.value.code == -4
+    m.model_forward(p, x, 9.0, 5, y)
+    m.model_backward(p, x, torch.ones_like(y), g)
+    torch.cuda.synchronize()
+    assert torch.isfinite(g).all()
+    m.close()
+
+
 FUSED_BACKWARD = [
     # conv + relu and conv + bn + relu (+ pool2) layers whose backward sums / masks are taken by the epilogue of the
     # input-gradient kernel of the layer above: LDS-patch kernel (256 tiles at 32 x 32), 1x1 layer, stride-2 forms
@@ -538,19 +560,21 @@ def test_backward_two_streams_same_bits(ae, dtype, spec, batch):
         assert np.array_equal(got[0], got[k]), "call %d differs from the single-stream result" % k
 
 
-def test_forward_and_backward_replay_from_a_captured_graph(ae):
+@pytest.mark.parametrize("name,dtype,batch", [("cfg2", "f32", 32), ("cfg5", "bf16", 4)])
+def test_forward_and_backward_replay_from_a_captured_graph(ae, name, dtype, batch):
     """The calls make no allocation and no host synchronisation, and the library's second stream is forked from and
     joined into the caller's by events, so a caller may capture them into a HIP graph: four replays, with eager calls
-    (same handle, other buffers) and synchronisations between them, each bit for bit the eager result."""
+    (same handle, other buffers) and synchronisations between them, each bit for bit the eager result.  The bf16
+    case takes the recomputing first layer and the fused backward epilogues."""
     import torch
-    cfg = wl.CONFIGS["cfg2"]
-    spec, batch = cfg["spec"], 32
-    m = ae.Model(spec, batch, ae.DTYPES["f32"])
-    params = torch.from_numpy(wl.make_params(spec, 11)).cuda()
-    x = torch.from_numpy(wl.make_input(spec, batch, 11)).cuda().contiguous()
-    y0 = torch.empty((batch,) + m.out_shape, device="cuda")
+    spec = wl.CONFIGS[name]["spec"]
+    bf = dtype == "bf16"
+    m = ae.Model(spec, batch, ae.DTYPES[dtype])
+    params = torch.from_numpy(wl.make_params(spec, 11, bf16=bf)).cuda()
+    x = to_dev(wl.make_input(spec, batch, 11, bf16=bf), dtype, torch)
+    y0 = torch.empty((batch,) + m.out_shape, device="cuda", dtype=x.dtype)
     y1 = torch.full_like(y0, float("nan"))
-    dy = torch.from_numpy(wl.make_cotangent((batch,) + m.out_shape, 11)).cuda().contiguous()
+    dy = to_dev(wl.make_cotangent((batch,) + m.out_shape, 11), dtype, torch)
     g0 = torch.empty(m.n_params, device="cuda")
     g1 = torch.full_like(g0, float("nan"))
 
