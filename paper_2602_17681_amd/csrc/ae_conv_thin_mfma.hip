@@ -772,12 +772,18 @@ __global__ __launch_bounds__(NT, (PASS == 3 && NJ == 2) ? 2 : 3) void k_thin_fir
     }
 
     if (PASS == 3) {
-      __syncthreads();                          // the slab is complete
+      // The pixel is the reduction index, so a wavefront may sum over any pixels as long as both operands name the
+      // same ones: it takes the 64 pixels whose gradients it has just written itself (its 16 pooling windows: two rows
+      // of 32 pixels, or four rows of 16 in a 16-wide patch), as four runs of 16 consecutive pixels of one patch row.
+      // No workgroup barrier: LDS operations of a wavefront complete in order.
+      asm volatile("" ::: "memory");          // (the compiler keeps the reads below behind the stores above)
       const int grp = lane >> 4, sl = lane & 15;
+      const int wpr = TW >> 5;                  // wavefronts side by side in a row pair (0: the patch is 16 wide)
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
-        const int p0 = wave * 64 + ks * 16;     // 16 consecutive pixels of one patch row
-        const int th = p0 >> tw_shift, tw0 = p0 & (TW - 1);
+        const int th = wpr ? 2 * (wave / wpr) + (ks >> 1) : 4 * wave + ks;
+        const int tw0 = wpr ? 32 * (wave % wpr) + 16 * (ks & 1) : 0;
+        const int p0 = th * TW + tw0;           // 16 consecutive pixels of one patch row
         const int psub = 8 * (grp >> 1) + (sl >> 2);
         t_bf16x8 a[NJ], bfr[2];
 #pragma unroll
