@@ -322,6 +322,8 @@ FUSED_BACKWARD = [
      "up2,conv3:3,sigmoid", 64),
     ("in:3x32x32,conv3:64,bn,relu,pool2,conv3:128,bn,relu,pool2,conv3:128,bn,relu,pool2,conv1:64,pnorm,awgn,conv1:128,relu,"
      "up2,conv3:128,relu,up2,conv3:64,relu,up2,conv3:3,sigmoid", 32),
+    # 128-wide images: the input-gradient kernels with the epilogues are the LDS-patch kernel on column strips
+    ("in:64x128x128,conv3:64,relu,conv3:64,bn,relu,conv3:64", 4),
 ]
 
 
@@ -377,7 +379,7 @@ def test_fused_backward_epilogues(ae, case, dead):
     assert_close(res[0], res[1], 1e-4, "gradients, fused epilogues against separate passes", tol_max=1e-3)
     import collections
     gone = collections.Counter(slots[1]) - collections.Counter(slots[0])
-    want = {0: (2, 2), 1: (2, 3)}[case]          # (bn_reduce passes, act_colsum passes) the epilogues replace
+    want = {0: (2, 2), 1: (2, 3), 2: (1, 1)}[case]          # (bn_reduce passes, act_colsum passes) the epilogues replace
     assert gone["bwd.bn_reduce"] == want[0] and gone["bwd.act_colsum"] == want[1], (gone, slots)
 
 
