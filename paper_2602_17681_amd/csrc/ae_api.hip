@@ -197,6 +197,7 @@ int pack_all(ae_model* m, const float* params, bool dgrad, hipStream_t s, int pa
     PackJob& j = pb.job[pb.n++];
     j.w = params + st.w_off; j.wp = dgrad ? st.wpack_d : st.wpack;
     j.cout = st.cout; j.cin = st.cin; j.k = st.k; j.dgrad = dgrad ? 1 : 0; j.first_block = 0;
+    j.frag = (dgrad ? st.wfrag_d : st.wfrag) ? 1 : 0;
     bytes += (double)st.cout * st.cin * st.k * st.k * (4.0 + (double)dtype_size(P.dtype));
   }
   if (pb.n > 0)
@@ -269,7 +270,7 @@ int forward_conv(ae_model* m, int si, Step& st, const float* params, const void*
               launch_pack_weights_up(params + st.w_off, st.wpack, st.cout, st.cin, P.dtype, CONV_UP_PHASES, s));
       else
         TIMED(si, "fwd.pack_weights", 0.0, wel * (4.0 + es),
-              launch_pack_weights(params + st.w_off, st.wpack, st.cout, st.cin, st.k, P.dtype, false, s));
+              launch_pack_weights(params + st.w_off, st.wpack, st.cout, st.cin, st.k, P.dtype, false, s, st.wfrag));
     }
     w = st.wpack;
   }
@@ -285,6 +286,7 @@ int forward_conv(ae_model* m, int si, Step& st, const float* params, const void*
   a.splitk_ws = m->splitk_ws;
   a.splitk_floats = P.max_splitk_floats;
   if (st.up_phases) a.geom = CONV_UP_PHASES;
+  a.w_frag = st.wfrag;
   int nblk = 0;
   const double conv_flops = 2.0 * raw_el * st.cin * st.k * st.k;
   const double conv_bytes = (in_el + raw_el + wel) * es;
@@ -568,12 +570,13 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
               launch_pack_weights_up(params + st.w_off, st.wpack_d, st.cout, st.cin, P.dtype, CONV_UP_DGRAD, s));
       else
         TIMED(si, "bwd.pack_weights", 0.0, wel * (4.0 + es),
-              launch_pack_weights(params + st.w_off, st.wpack_d, st.cout, st.cin, st.k, P.dtype, true, s));
+              launch_pack_weights(params + st.w_off, st.wpack_d, st.cout, st.cin, st.k, P.dtype, true, s, st.wfrag_d));
     }
     ConvArgs a;
     a.x = dr; a.w = st.wpack_d; a.bias = nullptr;
     a.y = (st.up && !st.up_dgrad) ? m->dfull : gnext;
     if (st.up_dgrad) a.geom = CONV_UP_DGRAD;   // straight to the stored resolution: no full-size gradient, no 2x2 sum
+    a.w_frag = st.wfrag_d;
     a.n = P.batch; a.hc = st.hc; a.wc = st.wc; a.cin = st.cout; a.cout = st.cin; a.k = st.k; a.up = 0;
     a.act = ACT_NONE; a.dtype = P.dtype; a.partial = nullptr; a.y_aux = nullptr;
     a.splitk_ws = m->splitk_ws;
@@ -662,16 +665,24 @@ int model_create(const char* layer_spec, int batch, int dtype, int bn_mode, ae_m
       st.mfma = conv_mfma_supported(a);
       st.recompute = st.thin == 1 && !st.needs_dx && st.has_bn && st.act == ACT_RELU && st.pool &&
                      thin_first_supported(st.cin, st.cout, st.k, st.up, P.dtype, st.hc, st.wc);
+      // the launches as forward_conv / backward_conv will describe them (of the pointers only null / non-null matters)
+      ConvArgs f = a;
+      f.act = (st.has_bn || st.pool) ? ACT_NONE : st.act;
+      f.partial = (st.has_bn && P.bn_mode == 0) ? (float*)m->ws : nullptr;
+      f.y_aux = (st.has_bn || st.pool) ? nullptr : st.aux;
+      ConvArgs d = a;
+      d.cin = st.cout; d.cout = st.cin; d.up = 0; d.act = ACT_NONE;
       if (st.mfma && st.thin == 0 && st.up && st.k == 3) {
         // the cheaper forms of an upsampled conv, decided once (the weight packing depends on it)
-        ConvArgs f = a;
-        f.act = (st.has_bn || st.pool) ? ACT_NONE : st.act;
-        f.partial = (st.has_bn && P.bn_mode == 0) ? (float*)m->ws : nullptr;   // only null / non-null matters here
-        f.y_aux = (st.has_bn || st.pool) ? nullptr : st.aux;
         st.up_phases = conv_up_phases_usable(f);
-        ConvArgs d = a;
-        d.cin = st.cout; d.cout = st.cin; d.up = 0; d.act = ACT_NONE;
         st.up_dgrad = st.needs_dx && conv_up_dgrad_usable(d);
+      }
+      if (st.mfma && st.thin == 0) {
+        // likewise the order of the packed weights
+        if (st.up_phases) f.geom = CONV_UP_PHASES;
+        if (st.up_dgrad) d.geom = CONV_UP_DGRAD;
+        st.wfrag = conv_weights_frag_order(f);
+        st.wfrag_d = st.needs_dx && conv_weights_frag_order(d);
       }
     }
   }

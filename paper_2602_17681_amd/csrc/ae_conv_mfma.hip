@@ -10,8 +10,9 @@
 //
 // One workgroup of 256 threads (4 wavefronts) computes a BM x BN tile with
 // v_mfma_f32_32x32x16_bf16 (bf16) or v_mfma_f32_32x32x2_f32 (fp32).  Kernels in this file:
-//   k_conv3_patch  3x3 convolutions of 16/32/64-wide images: the input patch of a tile lives in LDS
-//                  and all nine taps are read from it (one global read per input element)
+//   k_conv3_patch  3x3 convolutions of 16/32/64-wide images (wider ones by column strips): the input patch
+//                  of a tile lives in LDS and all nine taps are read from it (one global read per input
+//                  element); the weights, packed in MFMA fragment order, go straight into registers
 //   k_igemm        every other shape: per-tap slabs through a three-stage global-to-LDS ring,
 //                  optionally split over K; also the two cheaper forms of a 3x3 convolution behind
 //                  a x2 upsample (four 2x2 phase convolutions forward, one 4x4 stride-2
@@ -781,13 +782,12 @@ __global__ void k_splitk_finish(const float* __restrict__ partial, int splits, i
 }
 
 // wait until at most N LDS reads are outstanding, then hand the fragments to the compiler
-template <int N, int MI, int NJ>
-__device__ __forceinline__ void lds_wait_tie(uint4v (&a)[MI], uint4v (&b)[NJ]) {
+template <int N, int MI>
+__device__ __forceinline__ void lds_wait_tie_a(uint4v (&a)[MI]) {
 #if defined(__HIP_DEVICE_COMPILE__)
   asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N));
 #endif
   TieFrags<0, MI>::run(a);
-  TieFrags<0, NJ>::run(b);
 }
 template <typename T, int MI, int NJ>
 __device__ __forceinline__ void mma_group(const uint4v (&a)[MI], const uint4v (&b)[NJ], floatx16 (&acc)[MI][NJ]) {
@@ -813,27 +813,32 @@ struct Conv3Reads<N, N> {
 };
 
 // ---------------------------------------------------------------------------
-// 3x3 convolution with the input patch resident in LDS.
+// 3x3 convolution with the input patch resident in LDS and the weights straight in registers.
 //
 // The per-tap kernel above fetches every input pixel nine times (once per filter tap) through
 // the vector cache, whose 64 bytes per clock and compute unit then bound the MFMA rate.  Here a
 // workgroup owns TH = 256/W whole image rows (W = image width, a template parameter) and, for
 // each slab of 64 bytes of input channels, loads the (TH+2) x (W+2) patch of pixels around its
 // rows ONCE — zero padding included, delivered by the buffer range check — and forms all nine
-// taps from it: tap (r,s) of pixel (th,tw) is patch cell (th+r, tw+s).  Only the weights
-// (BN rows x 64 bytes per tap) still stream per tap, through a ring of three stages.
+// taps from it: tap (r,s) of pixel (th,tw) is patch cell (th+r, tw+s).
 //
 // LDS: the patch is double buffered, cells of 64 bytes stored linearly (the global-to-LDS load
 // writes lane l at base + 16*l), chunk c of cell q in slot c ^ ((q>>2)&3), so that the 16 cells
 // a fragment read touches per pass fall into 16 different 16-byte columns for any tap shift.
-// The K loop runs channel slab outer, tap inner (nine steps, fully unrolled, so that every
-// wait on the load counter is an immediate): step t waits for its own weight loads, the
-// barrier publishes them, then the weight loads of step t+2 and a share of the next slab's
-// patch loads are issued, then 2 x MI x NJ MFMAs.
+//
+// Weights never enter LDS (two wavefronts at most share a column, and the LDS port is what
+// the patch fragments need): they are packed in fragment order (ConvArgs::w_frag) — the 32
+// rows x 32 K-bytes block (nb, kb) is one KiB at (nb * K-bytes/32 + kb) KiB, lane l's MFMA
+// operand at byte 16 l of it — and a wave loads the operands of its own WN columns into
+// registers two steps ahead (ring of three stages; nine taps, so a tap always uses stage
+// tap % 3).  The K loop runs channel slab outer, tap inner (nine steps, fully unrolled); a
+// share of the next slab's patch loads is issued at taps 0..6.  The workgroup needs two
+// barriers per channel slab: before tap 8, when every wave's share of the next patch has
+// landed (tap 8 reads that patch's first fragments), and before tap 0, when every wave has
+// read its last fragments of the patch buffer that the loads issued from then on overwrite.
 // ---------------------------------------------------------------------------
 constexpr int patch_passes(int w) { return (((256 / w + 2) * (w + 2)) * 4 + 255) / 256; }
-// patch passes of the next channel slab issued at tap `tap` (spread over taps 0..6, so that the
-// slab is complete, in load order, before the first weight slab of the next channel slab)
+// patch passes of the next channel slab issued at tap `tap` (spread over taps 0..6)
 constexpr int passes_at(int passes, int tap) { return tap < 7 ? passes / 7 + (tap < passes % 7 ? 1 : 0) : 0; }
 constexpr int passes_before(int passes, int tap) {
   int n = 0;
@@ -852,13 +857,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   constexpr int PATCH_BYTES = PASSES * 4096;
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int MI = WM / 32, NJ = WN / 32;
-  constexpr int LB = BN / 64;                   // weight loads per thread and step
   constexpr int SW = WN + 16 / ES;
-  constexpr int OPER_BYTES = 2 * PATCH_BYTES + 3 * BN * BKB;
+  constexpr int OPER_BYTES = 2 * PATCH_BYTES;
   constexpr int EPI_BYTES = 4 * 32 * SW * ES + WGM * 2 * BN * 4;
   __shared__ __attribute__((aligned(64))) char smem[OPER_BYTES > EPI_BYTES ? OPER_BYTES : EPI_BYTES];
   char* const sP = smem;                        // [2][PATCH_BYTES]
-  char* const sB = smem + 2 * PATCH_BYTES;      // [3][BN*BKB]
   float (*sRed)[2][BN] = reinterpret_cast<float (*)[2][BN]>(smem + 4 * 32 * SW * ES);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -890,15 +893,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
     const unsigned pix = ((unsigned)img * (unsigned)Hin + (unsigned)(hh >> p.up)) * (unsigned)Win + (unsigned)(ww >> p.up);
     a_off[i] = ok ? pix * (unsigned)(p.Cin * ES) + (unsigned)chunk * 16u : kOob;
   }
-  // weight loader: thread t moves rows t/4 + 64*i, LDS slot t%4
-  const int lrow = tid >> 2;
-  const int gchunk = (tid & 3) ^ ((lrow >> 2) & 3);
-  unsigned b_off[LB];
+  // weight operands: one KiB block per 32 columns and K-step, this lane's 16 bytes of it
+  const unsigned kb32 = (unsigned)(p.K * ES) >> 5;
+  unsigned wv[NJ];
 #pragma unroll
-  for (int i = 0; i < LB; ++i) {
-    const int row = n0 + lrow + i * 64;
-    b_off[i] = row < p.N ? (unsigned)row * (unsigned)(p.K * ES) + (unsigned)gchunk * 16u : kOob;
-  }
+  for (int j = 0; j < NJ; ++j) wv[j] = ((((unsigned)(n0 + wn * WN)) >> 5) + (unsigned)j) * kb32 * 1024u + (unsigned)lane * 16u;
   // fragment geometry
   const int frag_row = lane & 31, fc = lane >> 5;
   unsigned cell0[MI];                           // patch cell of this lane's pixel for tap (0,0)
@@ -908,9 +907,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
     cell0[i] = (unsigned)((ml / W) * PW + (ml % W));
   }
   const unsigned lds_p = (unsigned)(size_t)(lds_char*)sP;
-  const unsigned lds_b = (unsigned)(size_t)(lds_char*)sB + (unsigned)(wn * WN * BKB) + (unsigned)(frag_row * BKB);
-  const unsigned bsw = (unsigned)((frag_row >> 2) & 3);
-  const unsigned b_lane0 = lds_b + (((unsigned)fc ^ bsw) << 4);          // K-step 0; K-step 1 is ^ 32
 
   floatx16 acc[MI][NJ];
 #pragma unroll
@@ -923,16 +919,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   const int NC = (p.Cin * ES) / BKB;            // channel slabs
   const unsigned tap_bytes = (unsigned)(p.Cin * ES);
 #define PATCH_DMA(BUF, PASS, CBYTE) dma_load16(rX, sP + (BUF) * PATCH_BYTES + (PASS) * 4096 + wave * 1024, a_off[PASS] + (CBYTE))
-#define WEIGHT_DMA(STG, KBYTE)                                                                               \
+#define WFRAG_LOAD(STG, KBYTE)                                                                               \
   {                                                                                                          \
-    _Pragma("unroll") for (int i = 0; i < LB; ++i)                                                           \
-        dma_load16(rW, sB + (STG) * BN * BKB + i * 4096 + wave * 1024, b_off[i] + (KBYTE));                  \
+    const unsigned so = ((KBYTE) >> 5) << 10;                                                                \
+    _Pragma("unroll") for (int j = 0; j < NJ; ++j) {                                                         \
+      bq[STG][0][j] = __builtin_amdgcn_raw_buffer_load_b128(rW, wv[j], so, 0);                               \
+      bq[STG][1][j] = __builtin_amdgcn_raw_buffer_load_b128(rW, wv[j], so + 1024u, 0);                       \
+    }                                                                                                        \
   }
-  // Fragment registers: set 0 holds K-step 0 of the current tap (read during the previous step),
-  // set 1 K-step 1 (read at the start of the step, behind the MFMAs of K-step 0); while the
-  // MFMAs of K-step 1 run, set 0 is refilled for the next tap.  The weights of step t+1 are
-  // therefore required (own loads done, then barrier) already at the start of step t.
-  uint4v f0a[MI], f0b[NJ], f1a[MI], f1b[NJ];
+  // Patch fragment registers: set 0 holds K-step 0 of the current tap (read during the previous step), set 1
+  // K-step 1 (read at the start of the step, behind the MFMAs of K-step 0); while the MFMAs of K-step 1 run,
+  // set 0 is refilled for the next tap.  The waits for the weight registers are the compiler's.
+  uint4v f0a[MI], f1a[MI];
+  uint4v bq[3][2][NJ];
 #define CONV3_ADDR(AA, CELLS, TAPV)                                                                          \
   _Pragma("unroll") for (int i = 0; i < MI; ++i) {                                                           \
     const unsigned cell = CELLS[i] + (unsigned)(((TAPV) / 3) * PW + (TAPV) % 3);                             \
@@ -941,67 +940,72 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   // prologue: the first patch, the weights of steps 0 and 1; fragments of (slab 0, tap 0, K-step 0)
 #pragma unroll
   for (int i = 0; i < PASSES; ++i) PATCH_DMA(0, i, 0u);
-  WEIGHT_DMA(0, 0u);
-  WEIGHT_DMA(1, tap_bytes);
-  __builtin_amdgcn_s_waitcnt(vm_imm(LB));
+  WFRAG_LOAD(0, 0u);
+  WFRAG_LOAD(1, tap_bytes);
+  __builtin_amdgcn_s_waitcnt(vm_imm(0));
   __builtin_amdgcn_s_barrier();
   {
     unsigned aa[MI];
     CONV3_ADDR(aa, cell0, 0)
-    LdsReadFrags<0, NJ, 32 * BKB>::run(f0b, b_lane0);
     Conv3Reads<0, MI>::run(f0a, aa, 0u);
   }
 
   // One step: tap TAP of channel slab c.  `last` = this is the last channel slab.
 #define CONV3_STEP(TAP)                                                                                      \
   {                                                                                                          \
-    if (!last) __builtin_amdgcn_s_waitcnt(vm_imm(passes_at(PASSES, ((TAP) + 8) % 9)));                       \
-    else __builtin_amdgcn_s_waitcnt(vm_imm(0));                                                              \
-    __builtin_amdgcn_s_barrier();                                                                            \
-    if (!last || (TAP) < 7)                                                                                  \
-      WEIGHT_DMA(((TAP) + 2) % 3, (unsigned)(((TAP) + 2) % 9) * tap_bytes + cbyte + ((TAP) >= 7 ? (unsigned)BKB : 0u)); \
+    if ((TAP) == 8 && !last) {                                                                               \
+      __builtin_amdgcn_s_waitcnt(vm_imm(2 * NJ));   /* (only the weights tap 7 asked for may be outstanding) */ \
+      __builtin_amdgcn_s_barrier();                                                                          \
+    }                                                                                                        \
+    if ((TAP) == 0 && c > 0) __builtin_amdgcn_s_barrier();                                                   \
     if (!last) {                                                                                             \
       _Pragma("unroll") for (int q = 0; q < passes_at(PASSES, (TAP)); ++q)                                   \
           PATCH_DMA(nbuf, passes_before(PASSES, (TAP)) + q, cbyte + (unsigned)BKB);                          \
     }                                                                                                        \
+    if (!last || (TAP) < 7)                                                                                  \
+      WFRAG_LOAD(((TAP) + 2) % 3, (unsigned)(((TAP) + 2) % 9) * tap_bytes + cbyte + ((TAP) >= 7 ? (unsigned)BKB : 0u)) \
     {                                                                                                        \
       unsigned aa[MI];                                                                                       \
       CONV3_ADDR(aa, cellb, (TAP))                                                                           \
-      LdsReadFrags<0, NJ, 32 * BKB>::run(f1b, (b_lane0 + (unsigned)(((TAP) % 3) * BN * BKB)) ^ 32u);         \
       Conv3Reads<0, MI>::run(f1a, aa, 32u);                                                                  \
     }                                                                                                        \
-    lds_wait_tie<MI + NJ, MI, NJ>(f0a, f0b);                                                                 \
-    mma_group<T, MI, NJ>(f0a, f0b, acc);                                                                     \
+    lds_wait_tie_a<MI, MI>(f0a);                                                                             \
+    mma_group<T, MI, NJ>(f0a, bq[(TAP) % 3][0], acc);                                                        \
     __builtin_amdgcn_sched_barrier(0);                                                                       \
-    lds_wait_tie<0, MI, NJ>(f1a, f1b);                                                                       \
+    lds_wait_tie_a<0, MI>(f1a);                                                                              \
     if (!(last && (TAP) == 8)) {                                                                             \
       unsigned aa[MI];                                                                                       \
       if ((TAP) == 8) { CONV3_ADDR(aa, celln, 0) } else { CONV3_ADDR(aa, cellb, ((TAP) + 1) % 9) }           \
-      LdsReadFrags<0, NJ, 32 * BKB>::run(f0b, b_lane0 + (unsigned)((((TAP) + 1) % 3) * BN * BKB));           \
       Conv3Reads<0, MI>::run(f0a, aa, 0u);                                                                   \
     }                                                                                                        \
     __builtin_amdgcn_sched_barrier(0);                                                                       \
-    mma_group<T, MI, NJ>(f1a, f1b, acc);                                                                     \
+    mma_group<T, MI, NJ>(f1a, bq[(TAP) % 3][1], acc);                                                        \
     __builtin_amdgcn_sched_barrier(0);                                                                       \
   }
-
-  for (int c = 0; c < NC; ++c) {
-    const bool last = c + 1 == NC;
-    const int nbuf = (c + 1) & 1;
-    unsigned cellb[MI], celln[MI];               // the buffer offset is a multiple of 4 cells: the swizzle bits are unchanged
-#pragma unroll
-    for (int i = 0; i < MI; ++i) {
-      cellb[i] = cell0[i] + (unsigned)((c & 1) * (PATCH_BYTES / 64));
-      celln[i] = cell0[i] + (unsigned)(nbuf * (PATCH_BYTES / 64));
-    }
-    const unsigned cbyte = (unsigned)(c * BKB);
-    CONV3_STEP(0) CONV3_STEP(1) CONV3_STEP(2) CONV3_STEP(3) CONV3_STEP(4)
-    CONV3_STEP(5) CONV3_STEP(6) CONV3_STEP(7) CONV3_STEP(8)
+  // (the last slab is a copy of its own with `last` a constant: where one body served both, the compiler's wait
+  // for a weight register had to assume the fewer loads in flight of the last slab, and stalled every other slab's
+  // taps 7 and 8 on loads issued a moment before)
+#define CONV3_SLAB(LASTV)                                                                                    \
+  {                                                                                                          \
+    constexpr bool last = LASTV;                                                                             \
+    const int nbuf = (c + 1) & 1;                                                                            \
+    unsigned cellb[MI], celln[MI];               /* (the buffer offset is a multiple of 4 cells: same swizzle bits) */ \
+    _Pragma("unroll") for (int i = 0; i < MI; ++i) {                                                         \
+      cellb[i] = cell0[i] + (unsigned)((c & 1) * (PATCH_BYTES / 64));                                        \
+      celln[i] = cell0[i] + (unsigned)(nbuf * (PATCH_BYTES / 64));                                           \
+    }                                                                                                        \
+    const unsigned cbyte = (unsigned)(c * BKB);                                                              \
+    CONV3_STEP(0) CONV3_STEP(1) CONV3_STEP(2) CONV3_STEP(3) CONV3_STEP(4)                                    \
+    CONV3_STEP(5) CONV3_STEP(6) CONV3_STEP(7) CONV3_STEP(8)                                                  \
   }
-#undef CONV3_ADDR
+  int c = 0;
+  for (; c + 1 < NC; ++c) CONV3_SLAB(false)
+  CONV3_SLAB(true)
+#undef CONV3_SLAB
 #undef CONV3_STEP
+#undef CONV3_ADDR
+#undef WFRAG_LOAD
 #undef PATCH_DMA
-#undef WEIGHT_DMA
   __syncthreads();                               // every wave is done with the operands: the epilogue reuses the memory
   igemm_epilogue<T, BM, BN, WGM, WGN, INTERIOR, EPI>(acc, p, smem, sRed, m0, n0, (int64_t)tile_m);
 }
@@ -1148,8 +1152,11 @@ int conv_comp_blocks(const ConvArgs& a0) {
   return (int)(M / t.bm);
 }
 
+bool conv_weights_frag_order(const ConvArgs& a) { return conv3_patch_usable(a); }
+
 int launch_conv_mfma(const ConvArgs& a0, hipStream_t s) {
   if (!conv_mfma_supported(a0)) return fail(AE_EINVAL, "conv_mfma: shape not supported");
+  if (a0.w_frag != conv3_patch_usable(a0)) return fail(AE_EINVAL, "conv_mfma: the order of the packed weights does not fit the kernel of this launch (conv_weights_frag_order)");
   if (a0.geom == CONV_UP_PHASES && !conv_up_phases_usable(a0)) return fail(AE_EINVAL, "conv_mfma: phase form not usable here");
   if (!conv_epi_usable(a0)) return fail(AE_EINVAL, "conv_mfma: epilogue variant not usable for this shape");
   const ConvArgs a = conv_effective(a0);

@@ -54,8 +54,18 @@ int transpose_impl(const void* in, void* out, int64_t batch, int rows, int cols,
 // weights: canonical fp32 W[co][ci][r][s] -> packed [co][r][s][ci] (forward) or
 // [ci][k-1-r][k-1-s][co] (the convolution that produces the input gradient)
 // ---------------------------------------------------------------------------
+// Element index of (row, k) of a packed [rows][K] matrix in MFMA fragment order: 32 rows x 32 bytes of K form one
+// KiB block, blocks of a row group follow each other along K, and inside a block lane 32 c + r of a wavefront
+// finds the 16-byte chunk c of row r at byte 16 (32 c + r) — a wave's operand loads are then 1 KiB contiguous.
 template <typename T>
-__global__ void k_pack_weights(const float* __restrict__ w, T* __restrict__ wp, int cout, int cin, int k, int dgrad) {
+__device__ __forceinline__ int64_t frag_order_index(int row, int64_t kidx, int64_t K) {
+  const int64_t kbyte = kidx * (int64_t)sizeof(T), kblocks = (K * (int64_t)sizeof(T)) >> 5;
+  const int64_t byte = (((int64_t)(row >> 5) * kblocks + (kbyte >> 5)) << 10) + ((((kbyte >> 4) & 1) * 32 + (row & 31)) << 4) + (kbyte & 15);
+  return byte / (int64_t)sizeof(T);
+}
+
+template <typename T>
+__global__ void k_pack_weights(const float* __restrict__ w, T* __restrict__ wp, int cout, int cin, int k, int dgrad, int frag) {
   const int64_t total = (int64_t)cout * cin * k * k;
   for (int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x; i < total; i += (int64_t)gridDim.x * NT) {
     // i enumerates the PACKED layout so that the stores coalesce
@@ -71,7 +81,8 @@ __global__ void k_pack_weights(const float* __restrict__ w, T* __restrict__ wp, 
       int r = (int)(t % k); int ci = (int)(t / k);
       src = (((int64_t)co * cin + ci) * k + (k - 1 - r)) * k + (k - 1 - s);
     }
-    Store<T>::st(wp + i, w[src]);
+    const int64_t K = (int64_t)(dgrad ? cout : cin) * k * k;
+    Store<T>::st(wp + (frag ? frag_order_index<T>((int)(i / K), i % K, K) : i), w[src]);
   }
 }
 
@@ -94,6 +105,10 @@ __global__ void k_pack_weights_batch(PackBatch pb) {
     if (i >= (int64_t)cout * cin) return;
     const int ci = (int)(i % cin), co = (int)(i / cin);
     const float* __restrict__ src = J.w + ((int64_t)co * cin + ci) * kk;
+    if (J.frag) {
+      for (int t = 0; t < kk; ++t) Store<T>::st(wp + frag_order_index<T>(co, (int64_t)t * cin + ci, (int64_t)kk * cin), src[t]);
+      return;
+    }
     for (int t = 0; t < kk; ++t) Store<T>::st(wp + ((int64_t)co * kk + t) * cin + ci, src[t]);
     return;
   }
@@ -112,8 +127,11 @@ __global__ void k_pack_weights_batch(PackBatch pb) {
     const int p = it * NT + threadIdx.x;
     const int co_l = p & 31, ci_l = p >> 5;
     if (co0 + co_l < cout && ci0 + ci_l < cin) {
-      for (int t = 0; t < kk; ++t)   // tap (r,s) -> (k-1-r, k-1-s)
-        Store<T>::st(wp + ((int64_t)(ci0 + ci_l) * kk + (kk - 1 - t)) * cout + co0 + co_l, tile[(co_l * 33 + ci_l) * kk + t]);
+      for (int t = 0; t < kk; ++t) {   // tap (r,s) -> (k-1-r, k-1-s)
+        const int64_t kidx = (int64_t)(kk - 1 - t) * cout + co0 + co_l;
+        const int64_t dst = J.frag ? frag_order_index<T>(ci0 + ci_l, kidx, (int64_t)kk * cout) : (int64_t)(ci0 + ci_l) * kk * cout + kidx;
+        Store<T>::st(wp + dst, tile[(co_l * 33 + ci_l) * kk + t]);
+      }
     }
   }
 }
@@ -772,10 +790,12 @@ int launch_pack_weights_batch(PackBatch& pb, int dtype, hipStream_t s) {
   return launch_status("pack_weights_batch");
 }
 
-int launch_pack_weights(const float* w, void* wp, int cout, int cin, int k, int dtype, bool for_dgrad, hipStream_t s) {
+int launch_pack_weights(const float* w, void* wp, int cout, int cin, int k, int dtype, bool for_dgrad, hipStream_t s, bool frag) {
   int64_t total = (int64_t)cout * cin * k * k;
+  if (frag && ((for_dgrad ? cin : cout) % 32 != 0 || ((int64_t)(for_dgrad ? cout : cin) * k * k * (int64_t)dtype_size(dtype)) % 32 != 0))
+    return fail(AE_EINVAL, "pack_weights: fragment order needs rows in 32s and K in 32-byte blocks");
   DISPATCH_T(dtype, hipLaunchKernelGGL((k_pack_weights<T>), dim3(grid_for(total, NT, 4096)), dim3(NT), 0, s, w, (T*)wp,
-                                       cout, cin, k, for_dgrad ? 1 : 0));
+                                       cout, cin, k, for_dgrad ? 1 : 0, frag ? 1 : 0));
   return launch_status("pack_weights");
 }
 

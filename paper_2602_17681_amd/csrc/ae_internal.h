@@ -69,6 +69,7 @@ struct Step {
   bool mfma = false;                // forward uses the MFMA implicit-GEMM kernel
   bool up_phases = false;           // forward of an upsampled conv as four 2x2 phase convolutions (CONV_UP_PHASES)
   bool up_dgrad = false;            // its input gradient as one 4x4 stride-2 convolution (CONV_UP_DGRAD)
+  bool wfrag = false, wfrag_d = false;   // packed weights of the forward / input-gradient conv in MFMA fragment order (conv_weights_frag_order)
   int thin = 0;                     // 1: thin-in kernels (input is the planar boundary tensor); 2: thin-out kernels
   bool recompute = false;           // thin-in + bn + relu + pool2: the conv output is recomputed by every pass that needs it, never stored
   bool out_planar = false;          // `out` is stored planar [n][C][H][W] (thin-out step)
@@ -124,9 +125,9 @@ int launch_transpose(const void* in, void* out, int64_t batch, int rows, int col
 int launch_to_f32_nchw(const void* in_nhwc, float* out_nchw, int64_t batch, int c, int hw, int dtype, hipStream_t s);
 
 // weights
-int launch_pack_weights(const float* w, void* wp, int cout, int cin, int k, int dtype, bool for_dgrad, hipStream_t s);
+int launch_pack_weights(const float* w, void* wp, int cout, int cin, int k, int dtype, bool for_dgrad, hipStream_t s, bool frag = false);
 // several layers in one launch
-struct PackJob { const float* w; void* wp; int cout, cin, k, dgrad; int64_t first_block; };
+struct PackJob { const float* w; void* wp; int cout, cin, k, dgrad; int64_t first_block; int frag; };   // frag: rows in MFMA fragment order
 constexpr int kMaxPackJobs = 32;
 struct PackBatch { int n; PackJob job[kMaxPackJobs]; };
 int launch_pack_weights_batch(PackBatch& pb, int dtype, hipStream_t s);
@@ -157,6 +158,10 @@ struct ConvArgs {
   const void* comp = nullptr;
   int comp_mode = 0;
   const float* comp_bn = nullptr;
+  // w is in MFMA fragment order (the packing kernels' `frag` form): the 32 rows x 32 K-bytes block (nb, kb) of the
+  // [rows][K] matrix is one KiB at (nb * K-bytes/32 + kb) KiB, row r's bytes 16c..16c+15 of it at 16 (32 c + r).
+  // Only where conv_weights_frag_order() says so (the kernel that loads its weights straight into registers).
+  bool w_frag = false;
   // Dense-GEMM epilogues (k = 1 layers whose tiles all lie inside the output, no split-K):
   //   CONV_EPI_MXQ    the stored output is MX block-quantised (blocks of mx_block columns, a power of two between the
   //                   elements of 16 bytes and 64; FP4 E2M1 elements);
@@ -192,6 +197,7 @@ enum { CONV_EPI_NONE = 0, CONV_EPI_MXQ = 1, CONV_EPI_RESID = 2 };
 bool conv_epi_usable(const ConvArgs& a);         // can launch_conv_mfma run a.epi for this shape?
 bool conv_up_phases_usable(const ConvArgs& a);   // a: the plain description (geom ignored)
 int conv_comp_blocks(const ConvArgs& a);
+bool conv_weights_frag_order(const ConvArgs& a);   // does this launch take its weights in fragment order (ConvArgs::w_frag)?
 bool conv_up_dgrad_usable(const ConvArgs& a);    // a: the plain description of the input-gradient conv at conv resolution
 // Summed weights of the two forms above from the canonical [cout][cin][3][3] fp32 weights.
 int launch_pack_weights_up(const float* w, void* wp, int cout, int cin, int dtype, int geom, hipStream_t s);

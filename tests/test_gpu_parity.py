@@ -686,6 +686,14 @@ def test_full_size_linear_layers(ae, case):
     run_case(spec, batch, dtype=dtype, seed=400 + case, snr_db=10.0)
 
 
+def test_network_with_more_layers_than_one_packing_launch_holds(ae):
+    """35 convolution layers: the weights of a pass are then repacked layer by layer instead of by one launch for all
+    (the other packing kernel) — among them two 3x3 layers that run with the input patch in LDS and take their weights
+    in MFMA fragment order, forward and input gradient."""
+    spec = "in:16x16x16,conv3:64,relu," + "conv1:32,relu,conv1:64,relu," * 16 + "conv3:64,relu,conv1:16"
+    run_case(spec, 256, dtype="f32", seed=77, snr_db=10.0, flips=True, tag="35 layers")
+
+
 def test_cfg3_full_size_forward_backward(ae):
     """cfg3 at its full size (batch 128, 3x64x64, bf16) as bench.py runs it: y and every saved activation against both
     oracles, every gradient of the training step (the upstream gradient is the MSE gradient) against the oracle."""
