@@ -1054,6 +1054,8 @@ bool conv_mfma_supported(const ConvArgs& a0) {
 // The patch kernel takes 3x3 convolutions whose image width is 16..128 (a power of two), whose
 // tiles of 256/W rows divide the image height, with enough tiles to fill the chip, and whose
 // epilogue needs no run-time checks.
+// column width of the patch kernel's tiles
+static int conv3_patch_bn(const ConvArgs& a) { return a.cout % 128 == 0 ? 128 : 64; }
 static bool conv3_patch_usable(const ConvArgs& a) {
   if (a.geom != CONV_PLAIN || a.k != 3 || !conv_mfma_supported(a)) return false;
   // (a 128-pixel-wide tile would need 96 KB of LDS, one workgroup per compute unit: wider images are cut into column
@@ -1063,7 +1065,7 @@ static bool conv3_patch_usable(const ConvArgs& a) {
   // channel slabs, 109 against 131 us with two)
   const int th = 256 / (a.wc > 64 ? 64 : a.wc);
   if (a.hc % th != 0 || a.cout % 64 != 0) return false;
-  const int bn = a.cout % 128 == 0 ? 128 : 64;
+  const int bn = conv3_patch_bn(a);
   const int64_t tiles = ((int64_t)a.n * a.hc * a.wc / 256) * (a.cout / bn);
   if (tiles < 256) return false;
   return !a.y_aux && a.act != ACT_SIGMOID && !(a.partial && a.act != ACT_NONE);
@@ -1200,7 +1202,7 @@ int launch_conv_mfma(const ConvArgs& a0, hipStream_t s) {
     p.x_bytes = (unsigned)((int64_t)a0.n * a0.hc * a0.wc * a.cin * es);
   }
   if (conv3_patch_usable(a0)) {
-    const int bn = a.cout % 128 == 0 ? 128 : 64;
+    const int bn = conv3_patch_bn(a);
     p.tiles_n = a.cout / bn;
     p.strips = a.wc > 64 ? a.wc / 64 : 1;
     p.log_wt = 6;                                // strips of 64 pixels
