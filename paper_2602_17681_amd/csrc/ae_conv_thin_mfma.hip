@@ -596,6 +596,19 @@ __global__ __launch_bounds__(NT, (PASS == 3 && NJ == 2) ? 2 : 3) void k_thin_fir
     be[j] = sc[j] * (c2 * is[j] * mu[j] - c1);
     s1[j] = 0.0f; s2[j] = 0.0f;
   }
+  // Every loop-invariant load has landed before the first patch is requested: the load counter completes in order, so
+  // a wait for one of these values at its first use inside the loop would, in every iteration, also wait for the
+  // next patch's loads issued just before (seen in the compiled kernel: s_waitcnt vmcnt(0) in the middle of the
+  // arithmetic).  A use here makes the compiler wait here, once.
+#if defined(__HIP_DEVICE_COMPILE__)
+#pragma unroll
+  for (int r = 0; r < 3; ++r)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) asm volatile("" : "+v"(bfrag[r][j]));
+#pragma unroll
+  for (int j = 0; j < NJ; ++j)
+    asm volatile("" : "+v"(bs[j]), "+v"(sc[j]), "+v"(sh[j]), "+v"(mu[j]), "+v"(is[j]), "+v"(al[j]), "+v"(be[j]));
+#endif
   t_floatx16 wacc[PASS == 3 ? NJ : 1][2];
   if (PASS == 3) {
 #pragma unroll
@@ -647,6 +660,12 @@ __global__ __launch_bounds__(NT, (PASS == 3 && NJ == 2) ? 2 : 3) void k_thin_fir
     __syncthreads();                            // the previous patch is fully consumed
     thin_patch_store(pre, tile, H, W, CT, h0 - 1, w0, TH + 2, TW);
     uint4 cm0 = gv0, cm1 = gv1;                 // (pass 4: the prefetch below overwrites gv0, gv1)
+#if defined(__HIP_DEVICE_COMPILE__)
+    // (a use here: the compiler waits for these two loads here, before the next patch is requested, instead of at
+    // their first use in the arithmetic, where the same wait would also cover the loads just issued)
+    if (PASS == 4)
+      asm volatile("" : "+v"(cm0.x), "+v"(cm0.y), "+v"(cm0.z), "+v"(cm0.w), "+v"(cm1.x), "+v"(cm1.y), "+v"(cm1.z), "+v"(cm1.w));
+#endif
     if (PASS == 2 || PASS == 3) {
       if (tid < GCH) *reinterpret_cast<uint4*>(&sG[tid * 8]) = gv0;
       if (GPT == 2 && NT + tid < GCH) *reinterpret_cast<uint4*>(&sG[(NT + tid) * 8]) = gv1;
