@@ -677,6 +677,10 @@ FULL_SIZE_LINEAR = [
     # (fp32; 128 and 256 wide, a height that is not a power of two)
     ("in:16x128x128,conv3:64,conv3:64", 4, "f32"),
     ("in:32x12x256,conv3:64,relu,conv3:128", 24, "bf16"),
+    # the patch kernel with an odd number of channel slabs (96 bf16 / 48 fp32 channels = 3 slabs of 64 bytes) and three
+    # 64-wide column tiles (192 output channels), 32- and 16-pixel-wide images; weights in fragment order throughout
+    ("in:96x32x32,conv3:192,conv3:64", 64, "bf16"),
+    ("in:48x16x16,conv3:64,conv3:128", 256, "f32"),
 ]
 
 
