@@ -251,7 +251,7 @@ int forward_conv(ae_model* m, int si, Step& st, const float* params, const void*
     if (thin_out_mfma_supported(st.cout, st.cin, st.k, P.dtype))
       TIMED(si, "fwd.conv_thin_out_mfma", 2.0 * raw_el * st.cin * st.k * st.k, (in_el + raw_el) * es,
             launch_thin_out_mfma(in, params + st.w_off, st.wpack, params + st.b_off, st.out, st.aux, P.batch, st.hc,
-                                 st.wc, st.cout, st.cin, st.up, st.act, s));
+                                 st.wc, st.cout, st.cin, st.up, st.act, P.dtype, s));
     else
       TIMED(si, "fwd.conv_thin_out", 2.0 * raw_el * st.cin * st.k * st.k, (in_el + raw_el) * es,
             launch_thin_out_conv(in, params + st.w_off, params + st.b_off, st.out, st.aux, P.batch, st.hc, st.wc, st.cout,

@@ -879,7 +879,8 @@ __global__ __launch_bounds__(NT, (PASS == 3 && NJ == 2) ? 2 : 3) void k_thin_fir
 // adds its nine terms Z[pixel under tap (r,s)][(r,s),ct] in a fixed order.
 // wz: bf16 [32*NJ][CW], row tap*CT + ct (zero rows beyond 9*CT).  out planar (+ optional fp32 copy).
 // ---------------------------------------------------------------------------
-__global__ void k_thin_pack_wz(const float* __restrict__ wcanon, bf16_t* __restrict__ wz, int CT, int CW, int rows) {
+template <typename T>
+__global__ void k_thin_pack_wz(const float* __restrict__ wcanon, T* __restrict__ wz, int CT, int CW, int rows) {
   const int i = blockIdx.x * NT + threadIdx.x;
   if (i >= rows * CW) return;
   const int cw = i % CW, col = i / CW;
@@ -888,15 +889,18 @@ __global__ void k_thin_pack_wz(const float* __restrict__ wcanon, bf16_t* __restr
     const int ct = col % CT, tap = col / CT;
     v = wcanon[((int64_t)ct * CW + cw) * 9 + tap];
   }
-  wz[i] = f32_to_bf16(v);
+  Store<T>::st(wz + i, v);
 }
 
-template <int NJ, int KS>   // 32*NJ >= 9*CT columns, CW = 16*KS wide channels
-__global__ __launch_bounds__(NT) void k_thin_out_mfma(const bf16_t* __restrict__ wide, const bf16_t* __restrict__ wz,
-                                                      const float* __restrict__ bias, bf16_t* __restrict__ out,
+// T = bf16: one K = 16 MFMA per 16-byte load.  T = float: a 16-byte load holds four channels; component c of the low
+// half-wave and component c of the high one are the two K values of a v_mfma_f32_32x32x2_f32 (wz uses the same pairing).
+template <typename T, int NJ, int KS>   // 32*NJ >= 9*CT columns, CW = KS * 32/sizeof(T) wide channels
+__global__ __launch_bounds__(NT) void k_thin_out_mfma(const T* __restrict__ wide, const T* __restrict__ wz,
+                                                      const float* __restrict__ bias, T* __restrict__ out,
                                                       float* __restrict__ out_f32, int Hq, int Wq, int CT, int up,
                                                       int act, int TW, int tw_shift, int tiles_w, int tiles_h) {
-  constexpr int CW = 16 * KS;
+  constexpr int CPL = 16 / (int)sizeof(T);      // channels per 16-byte load
+  constexpr int CW = 2 * CPL * KS;
   constexpr int ZS = 32 * NJ + 1;               // odd row stride: conflict-free column reads
   constexpr int MAXC = 352;                     // (TH+2)*(TW+2) <= 340 cells for TW in {8,16,32}, rounded up to 32
   constexpr int TPW = 3;                        // row tiles of 32 cells per wave (11 tiles over 4 waves)
@@ -919,19 +923,19 @@ __global__ __launch_bounds__(NT) void k_thin_out_mfma(const bf16_t* __restrict__
     const int pr = cell / PW, pc = cell - pr * PW;
     const int hh = h0 - 1 + pr, ww = w0 - 1 + pc;
     const bool ok = cell < cells && hh >= 0 && hh < Hq && ww >= 0 && ww < Wq;
-    const bf16_t* src = wide + (((int64_t)n * Hq + min(max(hh, 0), Hq - 1)) * Wq + min(max(ww, 0), Wq - 1)) * CW + g * 8;
+    const T* src = wide + (((int64_t)n * Hq + min(max(hh, 0), Hq - 1)) * Wq + min(max(ww, 0), Wq - 1)) * CW + g * CPL;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      av[t][ks] = *reinterpret_cast<const uint4*>(src + ks * 16);
+      av[t][ks] = *reinterpret_cast<const uint4*>(src + ks * 2 * CPL);
       if (!ok) { av[t][ks].x = 0u; av[t][ks].y = 0u; av[t][ks].z = 0u; av[t][ks].w = 0u; }
     }
   }
-  t_bf16x8 bw[KS][NJ];
+  uint4 bw[KS][NJ];
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
     for (int j = 0; j < NJ; ++j)
-      bw[ks][j] = *reinterpret_cast<const t_bf16x8*>(&wz[(j * 32 + frag_row) * CW + ks * 16 + g * 8]);
+      bw[ks][j] = *reinterpret_cast<const uint4*>(&wz[(j * 32 + frag_row) * CW + ks * 2 * CPL + g * CPL]);
 
 #pragma unroll
   for (int t = 0; t < TPW; ++t) {
@@ -944,10 +948,19 @@ __global__ __launch_bounds__(NT) void k_thin_out_mfma(const bf16_t* __restrict__
         for (int e = 0; e < 16; ++e) acc[j][e] = 0.0f;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        union { uint4 u; t_bf16x8 v; } a;
+        union { uint4 u; t_bf16x8 v; float f[4]; } a;
         a.u = av[t][ks];
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, bw[ks][j], acc[j], 0, 0, 0);
+        for (int j = 0; j < NJ; ++j) {
+          union { uint4 u; t_bf16x8 v; float f[4]; } b;
+          b.u = bw[ks][j];
+          if constexpr (sizeof(T) == 2) {
+            acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, b.v, acc[j], 0, 0, 0);
+          } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.f[c], b.f[c], acc[j], 0, 0, 0);
+          }
+        }
       }
 #pragma unroll
       for (int j = 0; j < NJ; ++j)
@@ -981,9 +994,9 @@ __global__ __launch_bounds__(NT) void k_thin_out_mfma(const bf16_t* __restrict__
 #pragma unroll
         for (int s_ = 0; s_ < 3; ++s_) v += sZ[(prow + ((x + s_ - 1) >> up) - (w0 - 1)) * ZS + (r * 3 + s_) * CT + ct];
       }
-      const float a = apply_act(bf16_to_f32(f32_to_bf16(v)), act);
+      const float a = apply_act(round_to_storage<T>(v), act);
       const int64_t o = ((int64_t)n * CT + ct) * HWc + (int64_t)y * Wc + x;
-      out[o] = f32_to_bf16(a);
+      Store<T>::st(out + o, a);
       if (out_f32) out_f32[o] = a;
     }
   }
@@ -1108,30 +1121,37 @@ int launch_thin_first(int pass, const void* thin, const float* wcanon, void* wfr
 }
 
 bool thin_out_mfma_supported(int ct, int cw, int k, int dtype) {
-  return dtype == AE_BF16 && k == 3 && ct >= 1 && ct <= 4 && (cw == 32 || cw == 64 || cw == 128);
+  if (k != 3 || ct < 1 || ct > 4) return false;
+  if (dtype == AE_BF16) return cw == 32 || cw == 64 || cw == 128;
+  return dtype == AE_F32 && (cw == 32 || cw == 64);   // (binary32: 128 wide channels would hold 192 registers of loads)
 }
 
-int64_t thin_out_wz_bytes(int ct, int cw) { return (int64_t)((9 * ct + 31) / 32) * 32 * cw * 2; }
+int64_t thin_out_wz_bytes(int ct, int cw) { return (int64_t)((9 * ct + 31) / 32) * 32 * cw * 4; }   // (sized for binary32)
 
 // wide: [n*hq*wq][cw] (hq = hc >> up); out: planar [n][ct][hc][wc] (+ fp32 copy); wz: scratch of thin_out_wz_bytes
 int launch_thin_out_mfma(const void* wide, const float* wcanon, void* wz, const float* bias, void* out, float* out_f32,
-                         int n, int hc, int wc, int ct, int cw, int up, int act, hipStream_t s) {
-  if (!thin_out_mfma_supported(ct, cw, 3, AE_BF16) || up < 0 || up > 1) return fail(AE_EINVAL, "thin_out_mfma: shape not supported");
-  if (((uintptr_t)wide & 15) != 0) return fail(AE_EINVAL, "thin_out_mfma: input must be 16-byte aligned");
+                         int n, int hc, int wc, int ct, int cw, int up, int act, int dtype, hipStream_t s) {
+  if (!thin_out_mfma_supported(ct, cw, 3, dtype) || up < 0 || up > 1) return fail(AE_EINVAL, "thin_out_mfma: shape not supported");
+  if ((((uintptr_t)wide | (uintptr_t)wz) & 15) != 0) return fail(AE_EINVAL, "thin_out_mfma: input and weight scratch must be 16-byte aligned");
   const int hq = hc >> up, wq = wc >> up;
   const ThinTile t = thin_tile(n, hq, wq, 32);  // squarer patches: less halo
   const int nj = (9 * ct + 31) / 32;
-  hipLaunchKernelGGL(k_thin_pack_wz, dim3((unsigned)((nj * 32 * cw + NT - 1) / NT)), dim3(NT), 0, s, wcanon, (bf16_t*)wz, ct,
-                     cw, nj * 32);
+  const dim3 pgrid((unsigned)((nj * 32 * cw + NT - 1) / NT));
+  if (dtype == AE_BF16) hipLaunchKernelGGL((k_thin_pack_wz<bf16_t>), pgrid, dim3(NT), 0, s, wcanon, (bf16_t*)wz, ct, cw, nj * 32);
+  else hipLaunchKernelGGL((k_thin_pack_wz<float>), pgrid, dim3(NT), 0, s, wcanon, (float*)wz, ct, cw, nj * 32);
   AE_TRY(launch_status("thin_pack_wz"));
-#define LAUNCH_TOM(NJV, KSV)                                                                                     \
-  hipLaunchKernelGGL((k_thin_out_mfma<NJV, KSV>), dim3((unsigned)t.blocks), dim3(NT), 0, s, (const bf16_t*)wide, \
-                     (const bf16_t*)wz, bias, (bf16_t*)out, out_f32, hq, wq, ct, up, act, t.tw, t.shift, t.tiles_w, t.tiles_h)
-#define LAUNCH_TOM_KS(NJV)                   \
-  switch (cw) {                              \
-    case 32: LAUNCH_TOM(NJV, 2); break;      \
-    case 64: LAUNCH_TOM(NJV, 4); break;      \
-    default: LAUNCH_TOM(NJV, 8); break;      \
+#define LAUNCH_TOM(T, NJV, KSV)                                                                                  \
+  hipLaunchKernelGGL((k_thin_out_mfma<T, NJV, KSV>), dim3((unsigned)t.blocks), dim3(NT), 0, s, (const T*)wide,   \
+                     (const T*)wz, bias, (T*)out, out_f32, hq, wq, ct, up, act, t.tw, t.shift, t.tiles_w, t.tiles_h)
+#define LAUNCH_TOM_KS(NJV)                                                         \
+  if (dtype == AE_BF16) {                                                          \
+    switch (cw) {                                                                  \
+      case 32: LAUNCH_TOM(bf16_t, NJV, 2); break;                                  \
+      case 64: LAUNCH_TOM(bf16_t, NJV, 4); break;                                  \
+      default: LAUNCH_TOM(bf16_t, NJV, 8); break;                                  \
+    }                                                                              \
+  } else {                                                                         \
+    if (cw == 32) LAUNCH_TOM(float, NJV, 4); else LAUNCH_TOM(float, NJV, 8);       \
   }
   if (nj == 1) { LAUNCH_TOM_KS(1) } else { LAUNCH_TOM_KS(2) }
 #undef LAUNCH_TOM_KS

@@ -241,7 +241,7 @@ int launch_thin_first(int pass, const void* thin, const float* wcanon, void* wfr
 bool thin_out_mfma_supported(int ct, int cw, int k, int dtype);
 int64_t thin_out_wz_bytes(int ct, int cw);
 int launch_thin_out_mfma(const void* wide, const float* wcanon, void* wz, const float* bias, void* out, float* out_f32,
-                         int n, int hc, int wc, int ct, int cw, int up, int act, hipStream_t s);
+                         int n, int hc, int wc, int ct, int cw, int up, int act, int dtype, hipStream_t s);
 bool thin_wgrad_mfma_supported(int ct, int cw, int wq, int dtype);
 int64_t thin_wgrad_mfma_workspace_floats(int n, int hq, int wq, int cw);
 int launch_thin_wgrad_mfma(const void* thin, const void* wide, float* workspace, float* dw_canonical, int n, int hq,
