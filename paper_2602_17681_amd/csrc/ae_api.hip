@@ -318,7 +318,7 @@ int forward_conv(ae_model* m, int si, Step& st, const float* params, const void*
     }
     TIMED(si, "fwd.conv_thin_in_mfma", conv_flops, conv_bytes,
           launch_thin_in_mfma(in, params + st.w_off, st.wpack, a.bias, a.y, a.partial, P.batch, st.hc, st.wc, st.cin,
-                              st.cout, 0, a.act, 0, s));
+                              st.cout, 0, a.act, 0, P.dtype, s));
   } else if (st.thin == 1) {
     if (st.has_bn && P.bn_mode == 0) {
       a.partial = m->partial;
@@ -518,7 +518,7 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
         // the 2x2 sum that undoes the upsample happens in the kernel's epilogue
         TIMED(si, "bwd.dgrad_thin_mfma", conv_flops, (raw_el + in_el) * es,
               launch_thin_in_mfma(dr, params + st.w_off, st.wpack_d, nullptr, gnext, nullptr, P.batch, st.hc, st.wc,
-                                  st.cout, st.cin, 1, ACT_NONE, st.up, s));
+                                  st.cout, st.cin, 1, ACT_NONE, st.up, P.dtype, s));
       } else {
         TIMED(si, "bwd.dgrad_thin", conv_flops, (raw_el + full_el) * es,
               launch_thin_in_conv(dr, params + st.w_off, nullptr, st.up ? m->dfull : gnext, nullptr, P.batch, st.hc,
@@ -1046,7 +1046,7 @@ int model_get_conv_output(ae_model* m, int step, int64_t chw[3], float* out_nchw
     // not kept by the forward pass: computed again, into the buffer the plan reserves for it
     const float* prm = (const float*)m->last_params;
     AE_TRY(launch_thin_in_mfma(m->last_x, prm + st.w_off, st.wpack, prm + st.b_off, st.raw, nullptr, P.batch, st.hc, st.wc,
-                               st.cin, st.cout, 0, ACT_NONE, 0, (hipStream_t)stream));
+                               st.cin, st.cout, 0, ACT_NONE, 0, P.dtype, (hipStream_t)stream));
   }
   return launch_to_f32_nchw(st.raw, out_nchw, P.batch, st.cout, st.hc * st.wc, P.dtype, (hipStream_t)stream);
 }

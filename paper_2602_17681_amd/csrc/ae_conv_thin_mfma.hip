@@ -94,11 +94,65 @@ __device__ __forceinline__ void thin_fill_patch(bf16_t* __restrict__ tile, const
   }
 }
 
+// The same patch for binary32: a cell is a pixel of 4 interleaved floats (16 bytes); the interior moves as 16-byte
+// loads of 4 pixels of one channel.
+__device__ __forceinline__ void thin_fill_patch(float* __restrict__ tile, const float* __restrict__ img, int H, int W,
+                                                int CT, int h_first, int w_first, int rows, int IW, bool vec) {
+  const int PW = IW + 4;
+  const int tid = threadIdx.x;
+  const int64_t HW = (int64_t)H * W;
+  if (vec) {
+    const int cpr = IW >> 2, cshift = 31 - __clz(cpr);   // IW is a power of two
+    for (int idx = tid; idx < rows * cpr; idx += NT) {
+      const int pr = idx >> cshift, c = idx & (cpr - 1);
+      const int hh = h_first + pr, ww = w_first + 4 * c;
+      const bool ok = hh >= 0 && hh < H && ww < W;
+      const int64_t off = (int64_t)min(max(hh, 0), H - 1) * W + min(ww, W - 4);
+      float v[4][4];
+#pragma unroll
+      for (int ci = 0; ci < 4; ++ci) {
+        const float4 t = *reinterpret_cast<const float4*>(img + (int64_t)min(ci, CT - 1) * HW + off);
+        const bool keep = ok && ci < CT;
+        v[ci][0] = keep ? t.x : 0.0f; v[ci][1] = keep ? t.y : 0.0f; v[ci][2] = keep ? t.z : 0.0f; v[ci][3] = keep ? t.w : 0.0f;
+      }
+      float* dst = tile + ((int64_t)pr * PW + 2 + 4 * c) * 4;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) *reinterpret_cast<float4*>(dst + 4 * k) = make_float4(v[0][k], v[1][k], v[2][k], v[3][k]);
+    }
+    for (int idx = NT - 1 - tid; idx < rows * 2; idx += NT) {
+      const int pr = idx >> 1, side = idx & 1;
+      const int hh = h_first + pr, ww = side ? w_first + IW : w_first - 1;
+      const bool ok = hh >= 0 && hh < H && ww >= 0 && ww < W;
+      const int64_t off = (int64_t)min(max(hh, 0), H - 1) * W + min(max(ww, 0), W - 1);
+      float e[4];
+#pragma unroll
+      for (int ci = 0; ci < 4; ++ci) {
+        const float t = img[(int64_t)min(ci, CT - 1) * HW + off];
+        e[ci] = (ok && ci < CT) ? t : 0.0f;
+      }
+      float* cell = tile + ((int64_t)pr * PW + (side ? IW + 2 : 0)) * 4;
+      const float4 px = make_float4(e[0], e[1], e[2], e[3]), zero = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+      *reinterpret_cast<float4*>(cell) = side ? px : zero;
+      *reinterpret_cast<float4*>(cell + 4) = side ? zero : px;
+    }
+  } else {
+    for (int i = tid; i < rows * PW * 4; i += NT) {
+      const int ci = i & 3, cell = i >> 2;
+      const int pc = cell % PW, pr = cell / PW;
+      const int hh = h_first + pr, ww = w_first - 2 + pc;
+      const bool ok = ci < CT && pc >= 1 && pc <= IW + 2 && hh >= 0 && hh < H && ww >= 0 && ww < W;
+      const float t = img[(int64_t)min(ci, CT - 1) * HW + (int64_t)min(max(hh, 0), H - 1) * W + min(max(ww, 0), W - 1)];
+      tile[i] = ok ? t : 0.0f;
+    }
+  }
+}
+
 // Weights of a thin-side conv as bf16 MFMA operand rows: wfrag[co][r][k], k = 4*s + ci
 // (zero where ci >= CT, s == 3 or co >= CW).
 //   Wk(co,ci,r,s) = W[co][ci][r][s]             (W canonical [CW][CT][3][3])
 //                 = W[ci][co][2-r][2-s]         (flip: W canonical [CT][CW][3][3], input gradient)
-__global__ void k_thin_pack_wfrag(const float* __restrict__ wcanon, bf16_t* __restrict__ wfrag, int CT, int CW,
+template <typename T>
+__global__ void k_thin_pack_wfrag(const float* __restrict__ wcanon, T* __restrict__ wfrag, int CT, int CW,
                                   int rows, int flip) {
   const int i = blockIdx.x * NT + threadIdx.x;
   if (i >= rows * 48) return;
@@ -108,7 +162,7 @@ __global__ void k_thin_pack_wfrag(const float* __restrict__ wcanon, bf16_t* __re
   if (co < CW && ci < CT && s_ < 3)
     v = flip ? wcanon[(((int64_t)ci * CW + co) * 3 + (2 - r)) * 3 + (2 - s_)]
              : wcanon[(((int64_t)co * CT + ci) * 3 + r) * 3 + s_];
-  wfrag[i] = f32_to_bf16(v);
+  Store<T>::st(wfrag + i, v);
 }
 
 // Row L (0..255) of a workgroup's 256 x CW output tile -> pixel of the TH x TW patch.
@@ -131,13 +185,14 @@ __device__ __forceinline__ void thin_row_pixel(int L, int TW, int tw_shift, int&
 // MODE 2: interior, ReLU;  MODE 3: interior, no activation.
 // Element e of lane l in tile (i,j): row wave*64 + i*32 + (e/4)*8 + (l/32)*4 + e%4, channel j*32 + l%32.
 // Rows are staged through wave-private LDS so that global stores are 16 bytes wide.
-template <int NJ, int MODE, bool UPSUM>
+template <typename T, int NJ, int MODE, bool UPSUM>
 __device__ __forceinline__ void thin_epilogue(const t_floatx16 (&acc)[2][NJ], const float (&bs)[NJ],
-                                              bf16_t* __restrict__ stage, bf16_t* __restrict__ out_n, int H, int W,
+                                              T* __restrict__ stage, T* __restrict__ out_n, int H, int W,
                                               int CW, int h0, int w0, int TW, int tw_shift, int act, bool want_stats,
                                               float (&s1)[NJ], float (&s2)[NJ]) {
-  constexpr int SW = NJ * 32 + 8;                // staging row stride
-  constexpr int CPR = NJ * 4;                    // 16-byte chunks per pixel
+  constexpr int EPC = 16 / (int)sizeof(T);       // elements per 16-byte chunk
+  constexpr int SW = NJ * 32 + EPC;              // staging row stride
+  constexpr int CPR = NJ * 32 / EPC;             // 16-byte chunks per pixel
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col_lane = lane & 31, row_lane = (lane >> 5) * 4;
 #pragma unroll
@@ -150,7 +205,7 @@ __device__ __forceinline__ void thin_epilogue(const t_floatx16 (&acc)[2][NJ], co
           const int lr = (e >> 2) * 8 + row_lane + (e & 3);
           float v = acc[i][j][e] + bs[j];
           if (MODE == 0) {
-            v = bf16_to_f32(f32_to_bf16(v));
+            v = round_to_storage<T>(v);
             if (want_stats) {
               int th, tw;
               thin_row_pixel<false>(wave * 64 + i * 32 + lr, TW, tw_shift, th, tw);
@@ -162,14 +217,14 @@ __device__ __forceinline__ void thin_epilogue(const t_floatx16 (&acc)[2][NJ], co
             }
             v = apply_act(v, act);
           } else if (MODE == 1) {
-            v = bf16_to_f32(f32_to_bf16(v));
+            v = round_to_storage<T>(v);
             const float d = v - bs[j];
             s1[j] += d;
             s2[j] = fmaf(d, d, s2[j]);
           } else if (MODE == 2) {
             v = fmaxf(v, 0.0f);                  // rounding is monotonic and keeps 0
           }
-          stage[lr * SW + j * 32 + col_lane] = f32_to_bf16(v);
+          Store<T>::st(&stage[lr * SW + j * 32 + col_lane], v);
         }
       }
 #pragma unroll
@@ -179,9 +234,9 @@ __device__ __forceinline__ void thin_epilogue(const t_floatx16 (&acc)[2][NJ], co
         int th, tw;
         thin_row_pixel<false>(wave * 64 + i * 32 + lr, TW, tw_shift, th, tw);
         const int hh = h0 + th, ww = w0 + tw;
-        if (MODE != 0 || (hh < H && ww < W && ch * 8 < CW))
-          *reinterpret_cast<uint4*>(out_n + ((int64_t)hh * W + ww) * CW + ch * 8) =
-              *reinterpret_cast<const uint4*>(&stage[lr * SW + ch * 8]);
+        if (MODE != 0 || (hh < H && ww < W && ch * EPC < CW))
+          *reinterpret_cast<uint4*>(out_n + ((int64_t)hh * W + ww) * CW + ch * EPC) =
+              *reinterpret_cast<const uint4*>(&stage[lr * SW + ch * EPC]);
       }
     } else {
       // 2x2 sums: the row quad (e%4 = 0..3) of a lane is one pixel group
@@ -191,7 +246,7 @@ __device__ __forceinline__ void thin_epilogue(const t_floatx16 (&acc)[2][NJ], co
         for (int eg = 0; eg < 4; ++eg) {
           const float v = ((acc[i][j][4 * eg] + bs[j]) + (acc[i][j][4 * eg + 1] + bs[j])) +
                           ((acc[i][j][4 * eg + 2] + bs[j]) + (acc[i][j][4 * eg + 3] + bs[j]));
-          stage[(eg * 2 + (lane >> 5)) * SW + j * 32 + col_lane] = f32_to_bf16(v);
+          Store<T>::st(&stage[(eg * 2 + (lane >> 5)) * SW + j * 32 + col_lane], v);
         }
       }
       const int Hq = H >> 1, Wq = W >> 1;
@@ -201,9 +256,9 @@ __device__ __forceinline__ void thin_epilogue(const t_floatx16 (&acc)[2][NJ], co
         const int g8 = idx / CPR, ch = idx % CPR;
         const int G = wave * 16 + i * 8 + g8;
         const int hq = (h0 >> 1) + (G >> (tw_shift - 1)), wq = (w0 >> 1) + (G & ((TW >> 1) - 1));
-        if (idx < 8 * CPR && (MODE != 0 || (hq < Hq && wq < Wq && ch * 8 < CW)))
-          *reinterpret_cast<uint4*>(out_n + ((int64_t)hq * Wq + wq) * CW + ch * 8) =
-              *reinterpret_cast<const uint4*>(&stage[g8 * SW + ch * 8]);
+        if (idx < 8 * CPR && (MODE != 0 || (hq < Hq && wq < Wq && ch * EPC < CW)))
+          *reinterpret_cast<uint4*>(out_n + ((int64_t)hq * Wq + wq) * CW + ch * EPC) =
+              *reinterpret_cast<const uint4*>(&stage[g8 * SW + ch * EPC]);
       }
     }
   }
@@ -215,15 +270,19 @@ __device__ __forceinline__ void thin_epilogue(const t_floatx16 (&acc)[2][NJ], co
 // 32x32 tile.  out: [n][H][W][CW], or with UPSUM [n][H/2][W/2][CW] holding 2x2 sums.
 // partial (optional): [patch][sum | sum of squares][CW] of the stored values.
 // ---------------------------------------------------------------------------
-template <int NJ, bool UPSUM>
-__global__ __launch_bounds__(NT) void k_thin_in_mfma(const bf16_t* __restrict__ thin, const bf16_t* __restrict__ wfrag,
-                                                     const float* __restrict__ bias, bf16_t* __restrict__ out,
+// T = float: a filter row is K = 16 as eight v_mfma_f32_32x32x2_f32: a lane's 16-byte read is one patch cell (a tap's four
+// channels), the low half-wave takes taps 0 and 2, the high one taps 1 and 3, and component c of both halves is one
+// MFMA's pair of K values (the weights are read the same way).
+template <typename T, int NJ, bool UPSUM>
+__global__ __launch_bounds__(NT) void k_thin_in_mfma(const T* __restrict__ thin, const T* __restrict__ wfrag,
+                                                     const float* __restrict__ bias, T* __restrict__ out,
                                                      float* __restrict__ partial, int H, int W, int CT, int CW, int act,
                                                      int TW, int tw_shift, int tiles_w, int tiles_h, int vec) {
   constexpr int MAXT = 408;                     // (TH+2)*(TW+4) cells for every TW in {8,...,64}
-  constexpr int SW = NJ * 32 + 8;
-  __shared__ __attribute__((aligned(16))) bf16_t tile[MAXT * 4];
-  __shared__ __attribute__((aligned(16))) bf16_t stage_all[4 * 32 * SW];
+  constexpr int SW = NJ * 32 + 16 / (int)sizeof(T);
+  constexpr bool F32 = sizeof(T) == 4;
+  __shared__ __attribute__((aligned(16))) T tile[MAXT * 4];
+  __shared__ __attribute__((aligned(16))) T stage_all[4 * 32 * SW];
   __shared__ float sRed[4][2][NJ * 32];
   const int TH = NT >> tw_shift;
   const int PW = TW + 4;
@@ -236,12 +295,20 @@ __global__ __launch_bounds__(NT) void k_thin_in_mfma(const bf16_t* __restrict__ 
   const int frag_row = lane & 31, g = lane >> 5;
   const int col_lane = lane & 31;
 
-  t_bf16x8 bfrag[3][NJ];
+  union Frag { uint4 u; t_bf16x8 v; float f[4]; };
+  Frag bfrag[3][NJ][F32 ? 2 : 1];
 #pragma unroll
   for (int r = 0; r < 3; ++r)
 #pragma unroll
-    for (int j = 0; j < NJ; ++j)
-      bfrag[r][j] = *reinterpret_cast<const t_bf16x8*>(&wfrag[((j * 32 + frag_row) * 3 + r) * 16 + g * 8]);
+    for (int j = 0; j < NJ; ++j) {
+      const T* wrow = &wfrag[((j * 32 + frag_row) * 3 + r) * 16];
+      if constexpr (F32) {
+        bfrag[r][j][0].u = *reinterpret_cast<const uint4*>(wrow + g * 4);
+        bfrag[r][j][1].u = *reinterpret_cast<const uint4*>(wrow + 8 + g * 4);
+      } else {
+        bfrag[r][j][0].u = *reinterpret_cast<const uint4*>(wrow + g * 8);
+      }
+    }
   float bs[NJ];
 #pragma unroll
   for (int j = 0; j < NJ; ++j) bs[j] = (bias && j * 32 + col_lane < CW) ? bias[j * 32 + col_lane] : 0.0f;
@@ -262,33 +329,48 @@ __global__ __launch_bounds__(NT) void k_thin_in_mfma(const bf16_t* __restrict__ 
     thin_row_pixel<UPSUM>(wave * 64 + i * 32 + frag_row, TW, tw_shift, th, tw);
 #pragma unroll
     for (int r = 0; r < 3; ++r) {
-      // k-chunk g: taps s = 2g, 2g+1 = cells tw + 1 + 2g, tw + 2 + 2g of patch row th + r
-      const bf16_t* src = &tile[((th + r) * PW + tw + 1 + 2 * g) * 4];
-      union { uint2 u[2]; t_bf16x8 v; } a;
-      a.u[0] = *reinterpret_cast<const uint2*>(src);
-      a.u[1] = *reinterpret_cast<const uint2*>(src + 4);
+      if constexpr (F32) {
+        // taps g and 2 + g = cells tw + 1 + g and tw + 3 + g of patch row th + r
+        const float* src = &tile[((th + r) * PW + tw + 1 + g) * 4];
+        Frag a0, a1;
+        a0.u = *reinterpret_cast<const uint4*>(src);
+        a1.u = *reinterpret_cast<const uint4*>(src + 8);
 #pragma unroll
-      for (int j = 0; j < NJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, bfrag[r][j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < NJ; ++j) {
+#pragma unroll
+          for (int c = 0; c < 4; ++c) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0.f[c], bfrag[r][j][0].f[c], acc[i][j], 0, 0, 0);
+#pragma unroll
+          for (int c = 0; c < 4; ++c) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1.f[c], bfrag[r][j][F32 ? 1 : 0].f[c], acc[i][j], 0, 0, 0);
+        }
+      } else {
+        // k-chunk g: taps s = 2g, 2g+1 = cells tw + 1 + 2g, tw + 2 + 2g of patch row th + r
+        const T* src = &tile[((th + r) * PW + tw + 1 + 2 * g) * 4];
+        union { uint2 u[2]; t_bf16x8 v; } a;
+        a.u[0] = *reinterpret_cast<const uint2*>(src);
+        a.u[1] = *reinterpret_cast<const uint2*>(src + 4);
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a.v, bfrag[r][j][0].v, acc[i][j], 0, 0, 0);
+      }
     }
   }
 
   float s1[NJ], s2[NJ];
 #pragma unroll
   for (int j = 0; j < NJ; ++j) { s1[j] = 0.0f; s2[j] = 0.0f; }
-  bf16_t* stage = stage_all + wave * (32 * SW);
+  T* stage = stage_all + wave * (32 * SW);
   const bool interior = h0 + TH <= H && w0 + TW <= W && CW == NJ * 32;
   if (UPSUM) {
-    bf16_t* out_n = out + (int64_t)n * (H >> 1) * (W >> 1) * CW;
-    if (interior) thin_epilogue<NJ, 3, true>(acc, bs, stage, out_n, H, W, CW, h0, w0, TW, tw_shift, act, false, s1, s2);
-    else thin_epilogue<NJ, 0, true>(acc, bs, stage, out_n, H, W, CW, h0, w0, TW, tw_shift, act, false, s1, s2);
+    T* out_n = out + (int64_t)n * (H >> 1) * (W >> 1) * CW;
+    if (interior) thin_epilogue<T, NJ, 3, true>(acc, bs, stage, out_n, H, W, CW, h0, w0, TW, tw_shift, act, false, s1, s2);
+    else thin_epilogue<T, NJ, 0, true>(acc, bs, stage, out_n, H, W, CW, h0, w0, TW, tw_shift, act, false, s1, s2);
   } else {
-    bf16_t* out_n = out + (int64_t)n * H * W * CW;
+    T* out_n = out + (int64_t)n * H * W * CW;
     const bool stats = partial != nullptr;
     if (!interior || act == ACT_SIGMOID || (stats && act != ACT_NONE))
-      thin_epilogue<NJ, 0, false>(acc, bs, stage, out_n, H, W, CW, h0, w0, TW, tw_shift, act, stats, s1, s2);
-    else if (stats) thin_epilogue<NJ, 1, false>(acc, bs, stage, out_n, H, W, CW, h0, w0, TW, tw_shift, act, true, s1, s2);
-    else if (act == ACT_RELU) thin_epilogue<NJ, 2, false>(acc, bs, stage, out_n, H, W, CW, h0, w0, TW, tw_shift, act, false, s1, s2);
-    else thin_epilogue<NJ, 3, false>(acc, bs, stage, out_n, H, W, CW, h0, w0, TW, tw_shift, act, false, s1, s2);
+      thin_epilogue<T, NJ, 0, false>(acc, bs, stage, out_n, H, W, CW, h0, w0, TW, tw_shift, act, stats, s1, s2);
+    else if (stats) thin_epilogue<T, NJ, 1, false>(acc, bs, stage, out_n, H, W, CW, h0, w0, TW, tw_shift, act, true, s1, s2);
+    else if (act == ACT_RELU) thin_epilogue<T, NJ, 2, false>(acc, bs, stage, out_n, H, W, CW, h0, w0, TW, tw_shift, act, false, s1, s2);
+    else thin_epilogue<T, NJ, 3, false>(acc, bs, stage, out_n, H, W, CW, h0, w0, TW, tw_shift, act, false, s1, s2);
     if (stats) {
 #pragma unroll
       for (int j = 0; j < NJ; ++j) {
@@ -1019,35 +1101,43 @@ bool vec_ok(const void* p, int w) { return w % 8 == 0 && ((uintptr_t)p & 15) == 
 }  // namespace
 
 bool thin_in_mfma_supported(int ct, int cw, int k, int up, int dtype) {
-  return dtype == AE_BF16 && k == 3 && !up && ct >= 1 && ct <= 4 && cw % 32 == 0 && cw <= 128;
+  if (k != 3 || up || ct < 1 || ct > 4 || cw % 32 != 0) return false;
+  // (binary32: the weight operands of 96 or 128 wide channels would not fit the registers beside the accumulators)
+  return dtype == AE_BF16 ? cw <= 128 : (dtype == AE_F32 && cw <= 64);
 }
 
 int thin_in_mfma_blocks(int n, int h, int w) { return thin_tile(n, h, w).blocks; }
 
-int64_t thin_wfrag_bytes(int cw) { return (int64_t)((cw + 31) / 32) * 32 * 48 * 2; }
+int64_t thin_wfrag_bytes(int cw) { return (int64_t)((cw + 31) / 32) * 32 * 48 * 4; }   // (sized for binary32)
 
 // thin: planar [n][ct][h][w]; out: [n*h*w][cw], or with upsum (h, w even) [n*(h/2)*(w/2)][cw] holding the
 // sums over 2x2 pixel groups.  wfrag: scratch of thin_wfrag_bytes(cw) bytes.
 int launch_thin_in_mfma(const void* thin, const float* wcanon, void* wfrag, const float* bias, void* out, float* partial,
-                        int n, int h, int w, int ct, int cw, int flip, int act, int upsum, hipStream_t s) {
-  if (!thin_in_mfma_supported(ct, cw, 3, 0, AE_BF16)) return fail(AE_EINVAL, "thin_in_mfma: shape not supported");
+                        int n, int h, int w, int ct, int cw, int flip, int act, int upsum, int dtype, hipStream_t s) {
+  if (!thin_in_mfma_supported(ct, cw, 3, 0, dtype)) return fail(AE_EINVAL, "thin_in_mfma: shape not supported");
   if (upsum && ((h | w) & 1 || partial || act != ACT_NONE)) return fail(AE_EINVAL, "thin_in_mfma: bad 2x2-sum request");
+  if ((((uintptr_t)wfrag | (uintptr_t)out) & 15) != 0) return fail(AE_EINVAL, "thin_in_mfma: output and weight scratch must be 16-byte aligned");
   const ThinTile t = thin_tile(n, h, w);
   const int nj = cw / 32;
-  hipLaunchKernelGGL(k_thin_pack_wfrag, dim3((unsigned)((nj * 32 * 48 + NT - 1) / NT)), dim3(NT), 0, s, wcanon,
-                     (bf16_t*)wfrag, ct, cw, nj * 32, flip);
+  const dim3 pgrid((unsigned)((nj * 32 * 48 + NT - 1) / NT));
+  if (dtype == AE_BF16) hipLaunchKernelGGL((k_thin_pack_wfrag<bf16_t>), pgrid, dim3(NT), 0, s, wcanon, (bf16_t*)wfrag, ct, cw, nj * 32, flip);
+  else hipLaunchKernelGGL((k_thin_pack_wfrag<float>), pgrid, dim3(NT), 0, s, wcanon, (float*)wfrag, ct, cw, nj * 32, flip);
   AE_TRY(launch_status("thin_pack_wfrag"));
   const int vec = vec_ok(thin, w) ? 1 : 0;
-#define LAUNCH_TIM(NJV, UPV)                                                                                     \
-  hipLaunchKernelGGL((k_thin_in_mfma<NJV, UPV>), dim3((unsigned)t.blocks), dim3(NT), 0, s, (const bf16_t*)thin,  \
-                     (const bf16_t*)wfrag, bias, (bf16_t*)out, partial, h, w, ct, cw, act, t.tw, t.shift,        \
+#define LAUNCH_TIM(T, NJV, UPV)                                                                                  \
+  hipLaunchKernelGGL((k_thin_in_mfma<T, NJV, UPV>), dim3((unsigned)t.blocks), dim3(NT), 0, s, (const T*)thin,    \
+                     (const T*)wfrag, bias, (T*)out, partial, h, w, ct, cw, act, t.tw, t.shift,                  \
                      t.tiles_w, t.tiles_h, vec)
-#define LAUNCH_TIM_NJ(UPV)              \
-  switch (nj) {                         \
-    case 1: LAUNCH_TIM(1, UPV); break;  \
-    case 2: LAUNCH_TIM(2, UPV); break;  \
-    case 3: LAUNCH_TIM(3, UPV); break;  \
-    default: LAUNCH_TIM(4, UPV); break; \
+#define LAUNCH_TIM_NJ(UPV)                                                              \
+  if (dtype == AE_BF16) {                                                               \
+    switch (nj) {                                                                       \
+      case 1: LAUNCH_TIM(bf16_t, 1, UPV); break;                                        \
+      case 2: LAUNCH_TIM(bf16_t, 2, UPV); break;                                        \
+      case 3: LAUNCH_TIM(bf16_t, 3, UPV); break;                                        \
+      default: LAUNCH_TIM(bf16_t, 4, UPV); break;                                       \
+    }                                                                                   \
+  } else {                                                                              \
+    if (nj == 1) LAUNCH_TIM(float, 1, UPV); else LAUNCH_TIM(float, 2, UPV);             \
   }
   if (upsum) { LAUNCH_TIM_NJ(true) } else { LAUNCH_TIM_NJ(false) }
 #undef LAUNCH_TIM_NJ
@@ -1058,7 +1148,7 @@ int launch_thin_in_mfma(const void* thin, const float* wcanon, void* wfrag, cons
 // First layer + batch-norm + ReLU + 2x2 max-pool with the convolution output recomputed in every
 // pass (k_thin_first).  Whole patches only; 32, 64 or 128 output channels.
 bool thin_first_supported(int ct, int cw, int k, int up, int dtype, int h, int w) {
-  if (!thin_in_mfma_supported(ct, cw, k, up, dtype) || (cw != 32 && cw != 64 && cw != 128) || w % 8 != 0) return false;
+  if (dtype != AE_BF16 || !thin_in_mfma_supported(ct, cw, k, up, dtype) || (cw != 32 && cw != 64 && cw != 128) || w % 8 != 0) return false;
   const ThinTile t = thin_tile(1, h, w);
   return t.tw >= 16 && h % t.th == 0 && w % t.tw == 0;
 }
@@ -1090,7 +1180,7 @@ int launch_thin_first(int pass, const void* thin, const float* wcanon, void* wfr
   const int nj = thin_first_nj(cw, pass);        // 32-channel column tiles per workgroup; more channels: several workgroup columns
   const int halves = cw / (nj * 32);
   if (wcanon) {
-    hipLaunchKernelGGL(k_thin_pack_wfrag, dim3((unsigned)((cw * 48 + NT - 1) / NT)), dim3(NT), 0, s, wcanon,
+    hipLaunchKernelGGL((k_thin_pack_wfrag<bf16_t>), dim3((unsigned)((cw * 48 + NT - 1) / NT)), dim3(NT), 0, s, wcanon,
                        (bf16_t*)wfrag, ct, cw, cw, pass == 4 ? 1 : 0);
     AE_TRY(launch_status("thin_pack_wfrag"));
   }

@@ -231,7 +231,7 @@ bool thin_in_mfma_supported(int ct, int cw, int k, int up, int dtype);
 int thin_in_mfma_blocks(int n, int h, int w);   // = number of partial-sum blocks it writes
 int64_t thin_wfrag_bytes(int cw);               // scratch for the repacked weights
 int launch_thin_in_mfma(const void* thin, const float* wcanon, void* wfrag, const float* bias, void* out, float* partial,
-                        int n, int h, int w, int ct, int cw, int flip, int act, int upsum, hipStream_t s);
+                        int n, int h, int w, int ct, int cw, int flip, int act, int upsum, int dtype, hipStream_t s);
 // first layer + batch-norm + ReLU + pool2 with the convolution output recomputed in every pass
 bool thin_first_supported(int ct, int cw, int k, int up, int dtype, int h, int w);
 int thin_first_blocks(int n, int h, int w, int cw, int pass);   // = partial blocks pass 0 / 2 write
