@@ -112,6 +112,36 @@ def test_small_networks_forward_backward(ae, case, dtype):
              grad_tol=5e-2 if dtype == "bf16" else None)
 
 
+THIN_RAGGED = [
+    # the matrix-core kernels of the thin layers (first layer, last layer and its input gradient) on patches that
+    # stick out of the image, widths that rule out 16-byte loads, 32 and 64 wide channels, through an upsample and not
+    ("in:3x12x20,conv3:32,relu,conv3:3,sigmoid", 3),
+    ("in:2x10x12,conv3:64,bn,relu,pool2,up2,conv3:2,sigmoid", 4),
+    ("in:4x16x24,conv3:64,relu,conv3:4", 2),
+]
+
+
+@pytest.mark.parametrize("case", range(len(THIN_RAGGED)))
+def test_thin_layers_on_ragged_images_binary32(ae, case):
+    import torch
+    spec, batch = THIN_RAGGED[case]
+    run_case(spec, batch, dtype="f32", seed=120 + case, snr_db=7.0)
+    # ... and those kernels are the ones that ran
+    m = ae.Model(spec, batch, ae.AE_F32, 0)
+    p = torch.from_numpy(wl.make_params(spec, 120 + case, perturb=True)).cuda()
+    x = torch.from_numpy(wl.make_input(spec, batch, 120 + case)).cuda()
+    y = torch.empty((batch,) + m.out_shape, device="cuda")
+    g = torch.empty((m.n_params,), device="cuda")
+    m.model_timing_reset()
+    m.model_timing_enable(True)
+    m.model_forward(p, x, 7.0, 120 + case, y)
+    m.model_backward(p, x, torch.ones_like(y), g)
+    m.model_timing_enable(False)
+    names = {t["name"].split(".", 1)[1] for t in m.model_timing_read() if t["launches"]}
+    m.close()
+    assert {"fwd.conv_thin_in_mfma", "fwd.conv_thin_out_mfma", "bwd.dgrad_thin_mfma"} <= names, sorted(names)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_stored_statistics_batch_norm(ae, dtype):
     run_case("in:3x8x8,conv3:8,bn,relu,pool2,conv1:4,sigmoid", 4, dtype=dtype, seed=5, bn_mode=1)
