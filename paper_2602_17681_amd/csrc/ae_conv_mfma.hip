@@ -1697,6 +1697,38 @@ __device__ __forceinline__ void tr_read(TrFrag& f, unsigned addr, int row_bytes4
   asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(f.hi) : "v"(addr + (unsigned)row_bytes4), "n"(OFF));
 #endif
 }
+// The patch operand of a K-step for all taps of a filter row at once: pixels 0..11 of a lane's channel, from the
+// lane's cell on.  Tap s of pixel j reads cell j + s, so the operand of tap s is pixels s .. s+7 of this run: the taps
+// are cut out of one 12-pixel read in registers (funnel shifts for the odd tap) instead of being read from LDS once
+// each — three 8-byte reads per K-step instead of six, on the port that bounds this kernel.
+struct TrRun { uint2v lo, hi, ex; };            // pixels 0..3, 4..7, 8..11
+template <int OFF>
+__device__ __forceinline__ void tr_read_run(TrRun& f, unsigned addr) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(f.lo) : "v"(addr), "n"(OFF));
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(f.hi) : "v"(addr + 4u * 128u), "n"(OFF));
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(f.ex) : "v"(addr + 8u * 128u), "n"(OFF));
+#endif
+}
+template <int NTAP>
+__device__ __forceinline__ void tr_run_taps(TrRun& f, bf16x8 (&bv)[NTAP]) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile("" : "+v"(f.lo), "+v"(f.hi), "+v"(f.ex));
+#endif
+  const unsigned d0 = f.lo[0], d1 = f.lo[1], d2 = f.hi[0], d3 = f.hi[1], d4 = f.ex[0];
+  union { unsigned w[4]; bf16x8 v; } u;
+  u.w[0] = d0; u.w[1] = d1; u.w[2] = d2; u.w[3] = d3;
+  bv[0] = u.v;
+  if (NTAP > 1) {
+    u.w[0] = __builtin_amdgcn_alignbit(d1, d0, 16); u.w[1] = __builtin_amdgcn_alignbit(d2, d1, 16);
+    u.w[2] = __builtin_amdgcn_alignbit(d3, d2, 16); u.w[3] = __builtin_amdgcn_alignbit(d4, d3, 16);
+    bv[1] = u.v;
+  }
+  if (NTAP > 2) {
+    u.w[0] = d1; u.w[1] = d2; u.w[2] = d3; u.w[3] = d4;
+    bv[NTAP > 2 ? 2 : 0] = u.v;
+  }
+}
 __device__ __forceinline__ bf16x8 tr_value(TrFrag& f) {
 #if defined(__HIP_DEVICE_COMPILE__)
   asm volatile("" : "+v"(f.lo), "+v"(f.hi));
@@ -1719,9 +1751,9 @@ struct Wgrad3 {
   static constexpr int cell_base(int ks) { return ((ks * 16) / SW) * PCW + (ks * 16) % SW; }
 };
 
-// fragments of one K-step: MI of dY, NTAP (taps) of the patch
-template <int BM, int SW, int KS, int NTAP>
-__device__ __forceinline__ void wgrad3_reads(TrFrag (&fa)[BM / 64], TrFrag (&fb)[NTAP], unsigned a_addr, const unsigned (&b_addr)[NTAP]) {
+// fragments of one K-step: MI of dY, the patch run that holds every tap (b_addr: the lane's address for tap 0)
+template <int BM, int SW, int KS>
+__device__ __forceinline__ void wgrad3_reads(TrFrag (&fa)[BM / 64], TrRun& fb, unsigned a_addr, unsigned b_addr) {
   typedef Wgrad3<BM, SW> G;
 #pragma unroll
   for (int i = 0; i < G::MI; ++i) {
@@ -1729,8 +1761,7 @@ __device__ __forceinline__ void wgrad3_reads(TrFrag (&fa)[BM / 64], TrFrag (&fb)
     if (i == 0) tr_read<KS * 16 * G::RBA>(fa[0], a_addr, 4 * G::RBA);
     else tr_read<KS * 16 * G::RBA>(fa[i], a_addr ^ 64u, 4 * G::RBA);
   }
-#pragma unroll
-  for (int s_ = 0; s_ < NTAP; ++s_) tr_read<G::cell_base(KS) * 128>(fb[s_], b_addr[s_], 4 * 128);
+  tr_read_run<G::cell_base(KS) * 128>(fb, b_addr);
 }
 
 // UP2: the convolution reads its input through a x2 nearest-neighbour upsample.  An output pixel (2i+a, 2j+b) then
@@ -1747,7 +1778,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   typedef Wgrad3<BM, SW> G;
   constexpr int MI = G::MI;
   constexpr int NTAP = UP2 ? 2 : 3;
-  __shared__ __attribute__((aligned(1024))) char smem[3 * G::STAGE];   // XOR address arithmetic below needs the alignment
+  // (XOR address arithmetic below needs the alignment; 256 bytes of slack: the last pixels of a patch run may lie one
+  // cell past the last stage's patch — they are read, never used)
+  __shared__ __attribute__((aligned(1024))) char smem[3 * G::STAGE + 256];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   int b = xcd_logical_block((int)blockIdx.x, (int)gridDim.x);
@@ -1823,14 +1856,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   const int a_col = G::RBA == 256 ? (2 * wm) : wm;                       // 64-byte column of the wave's first 32 channels
   const int a_sw = G::RBA == 256 ? (lp & 3) : ((lp >> 1) & 1);
   const unsigned a_lane = (unsigned)(lp * G::RBA + ((a_col ^ a_sw) << 6) + 32 * (grp & 1) + 8 * (sl & 3));
-  unsigned b_lane[NTAP];
-#pragma unroll
-  for (int s_ = 0; s_ < NTAP; ++s_) {
+  unsigned b_lane;                               // tap 0; tap s is s cells further (tr_run_taps)
+  {
     // (UP2: tap v of column parity b reads stored column j + v - (1-b): the view shifted by b + v - 1)
     // (SW = 8: the 16 pixels of a K-step are two segment rows of the patch, PCW cells apart)
     const int lp_cell = SW >= 16 ? lp : (lp / SW) * G::PCW + lp % SW;
-    const int cell = 1 + s_ + (UP2 ? par_b : 0) + lp_cell;   // + cell_base(ks) (a multiple of 4) + 4 for the second half
-    b_lane[s_] = (unsigned)(G::A_BYTES + cell * 128 + ((wn ^ ((cell >> 1) & 1)) << 6) + 32 * (grp & 1) + 8 * (sl & 3));
+    const int cell = 1 + (UP2 ? par_b : 0) + lp_cell;   // + cell_base(ks) (a multiple of 4), + 4 and + 8 for the next pixels
+    b_lane = (unsigned)(G::A_BYTES + cell * 128 + ((wn ^ ((cell >> 1) & 1)) << 6) + 32 * (grp & 1) + 8 * (sl & 3));
   }
 
   floatx16 acc[NTAP][MI];
@@ -1841,16 +1873,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[s_][i][e] = 0.0f;
 
-  [[maybe_unused]] TrFrag fa0[MI], fb0[NTAP], fa1[MI], fb1[NTAP];   // (used by the device pass only)
-  [[maybe_unused]] constexpr int NR = 2 * (MI + NTAP);               // LDS reads per K-step
+  [[maybe_unused]] TrFrag fa0[MI], fa1[MI];      // (used by the device pass only)
+  [[maybe_unused]] TrRun fb0, fb1;
+  [[maybe_unused]] constexpr int NR = 2 * MI + 3;                    // LDS reads per K-step
 #define WGRAD3_MMA(FA, FB)                                                                                   \
   {                                                                                                          \
-    bf16x8 av[MI];                                                                                           \
+    bf16x8 av[MI], bv[NTAP];                                                                                 \
     _Pragma("unroll") for (int i = 0; i < MI; ++i) av[i] = tr_value(FA[i]);                                  \
+    tr_run_taps<NTAP>(FB, bv);                                                                               \
     _Pragma("unroll") for (int s_ = 0; s_ < NTAP; ++s_) {                                                    \
-      const bf16x8 bv = tr_value(FB[s_]);                                                                    \
       _Pragma("unroll") for (int i = 0; i < MI; ++i)                                                         \
-          acc[s_][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv, acc[s_][i], 0, 0, 0);              \
+          acc[s_][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[s_], acc[s_][i], 0, 0, 0);          \
     }                                                                                                        \
     __builtin_amdgcn_sched_barrier(0);                                                                       \
   }
@@ -1861,12 +1894,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
   if (KT > 1) WGRAD3_DMA(1);
   __builtin_amdgcn_s_waitcnt(vm_imm(0));
   __builtin_amdgcn_s_barrier();
-  {
-    unsigned ba[NTAP];
-#pragma unroll
-    for (int s_ = 0; s_ < NTAP; ++s_) ba[s_] = lds0 + b_lane[s_];
-    wgrad3_reads<BM, SW, 0, NTAP>(fa0, fb0, lds0 + a_lane, ba);
-  }
+  wgrad3_reads<BM, SW, 0>(fa0, fb0, lds0 + a_lane, lds0 + b_lane);
   int cur = 0;
   for (int t = 0; t < KT; ++t) {
     // the loads of slab t+1 (issued one slab ago) are the only ones outstanding
@@ -1875,22 +1903,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
     const int nxt = cur == 2 ? 0 : cur + 1;
     if (t + 2 < KT) { const int st2 = nxt == 2 ? 0 : nxt + 1; WGRAD3_DMA(st2); }
     [[maybe_unused]] const unsigned sa = lds0 + (unsigned)(cur * G::STAGE) + a_lane;
-    unsigned sb[NTAP], nb[NTAP];
-#pragma unroll
-    for (int s_ = 0; s_ < NTAP; ++s_) { sb[s_] = lds0 + (unsigned)(cur * G::STAGE) + b_lane[s_]; nb[s_] = lds0 + (unsigned)(nxt * G::STAGE) + b_lane[s_]; }
+    [[maybe_unused]] const unsigned sb = lds0 + (unsigned)(cur * G::STAGE) + b_lane, nb = lds0 + (unsigned)(nxt * G::STAGE) + b_lane;
     [[maybe_unused]] const unsigned na = lds0 + (unsigned)(nxt * G::STAGE) + a_lane;
 #if defined(__HIP_DEVICE_COMPILE__)
-    wgrad3_reads<BM, SW, 1, NTAP>(fa1, fb1, sa, sb);
+    wgrad3_reads<BM, SW, 1>(fa1, fb1, sa, sb);
     LGKM_WAIT(NR);
     WGRAD3_MMA(fa0, fb0)
-    wgrad3_reads<BM, SW, 2, NTAP>(fa0, fb0, sa, sb);
+    wgrad3_reads<BM, SW, 2>(fa0, fb0, sa, sb);
     LGKM_WAIT(NR);
     WGRAD3_MMA(fa1, fb1)
-    wgrad3_reads<BM, SW, 3, NTAP>(fa1, fb1, sa, sb);
+    wgrad3_reads<BM, SW, 3>(fa1, fb1, sa, sb);
     LGKM_WAIT(NR);
     WGRAD3_MMA(fa0, fb0)
     if (t + 1 < KT) {
-      wgrad3_reads<BM, SW, 0, NTAP>(fa0, fb0, na, nb);
+      wgrad3_reads<BM, SW, 0>(fa0, fb0, na, nb);
       LGKM_WAIT(NR);
     } else {
       LGKM_WAIT(0);
