@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0
 TRAFFIC = {
     # workload -> kernel family -> measured HBM bytes per launch
     "cfg5": {"k_igemm": {"bytes_per_launch": 93.3e6,
-                         "source": "profiles/cfg5_hbm_traffic.md (kernels as of commit 9177121; 20 launches per step, "
+                         "source": "profiles/cfg5_hbm_traffic.md (kernels as of commit e674093; 20 launches per step, "
                                    "59.4 MB fetched + 33.8 MB written each)"}},
 }
 
