@@ -488,7 +488,7 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
     if (thin_wgrad_mfma_supported(st.cout, st.cin, st.win, P.dtype))
       TIMED_ON(ws, si, "bwd.wgrad_thin_mfma", conv_flops, (in_el + raw_el) * es + wel * 4,
                launch_thin_wgrad_mfma(dr, in, m->wgrad_ws, grads + st.w_off, P.batch, st.hin, st.win, st.cout, st.cin, 1,
-                                      st.up, ws));
+                                      st.up, P.dtype, ws));
     else
       TIMED_ON(ws, si, "bwd.wgrad_thin", conv_flops, (in_el + raw_el) * es + wel * 4,
                launch_thin_wgrad(dr, in, m->wgrad_ws, grads + st.w_off, P.batch, st.hin, st.win, st.cout, st.cin, 1, st.up,
@@ -539,7 +539,7 @@ int backward_conv(ae_model* m, int si, Step& st, const float* params, const void
   if (st.thin == 1) {
     if (thin_wgrad_mfma_supported(st.cin, st.cout, st.wc, P.dtype))
       TIMED_ON(ws, si, "bwd.wgrad_thin_mfma", conv_flops, (in_el + raw_el) * es + wel * 4,
-               launch_thin_wgrad_mfma(in, dr, m->wgrad_ws, grads + st.w_off, P.batch, st.hc, st.wc, st.cin, st.cout, 0, 0, ws));
+               launch_thin_wgrad_mfma(in, dr, m->wgrad_ws, grads + st.w_off, P.batch, st.hc, st.wc, st.cin, st.cout, 0, 0, P.dtype, ws));
     else
       TIMED_ON(ws, si, "bwd.wgrad_thin", conv_flops, (in_el + raw_el) * es + wel * 4,
                launch_thin_wgrad(in, dr, m->wgrad_ws, grads + st.w_off, P.batch, st.hc, st.wc, st.cin, st.cout, 0, 0,

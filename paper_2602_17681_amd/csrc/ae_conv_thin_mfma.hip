@@ -412,16 +412,22 @@ __device__ __forceinline__ t_bf16x8 thin_tr_frag(const bf16_t* p0, const bf16_t*
   return u.v;
 }
 
-template <int MI>   // CW = 32*MI wide channels
-__global__ __launch_bounds__(NT) void k_thin_wgrad_mfma(const bf16_t* __restrict__ thin, const bf16_t* __restrict__ wide,
+// T = float: v_mfma_f32_32x32x2_f32, two pixels per step: lane l supplies pixel l/32 of the pair — wide channel l%32 of
+// it for one operand, column k = l%32 of B for the other, both plain 4-byte LDS reads (no transposition needed: the
+// 32 lanes of a half-wave read 32 consecutive channels, or the 2 x 16 values of two patch rows).  Behind an upsample
+// the four terms of B are added before the MFMA.
+template <typename T, int MI>   // CW = 32*MI wide channels
+__global__ __launch_bounds__(NT) void k_thin_wgrad_mfma(const T* __restrict__ thin, const T* __restrict__ wide,
                                                         float* __restrict__ partial, int Hq, int Wq, int CT, int up,
                                                         int TW, int tw_shift, int tiles_w, int tiles_h, int ntiles,
                                                         int vec) {
+  constexpr bool F32 = sizeof(T) == 4;
+  constexpr int EPC = 16 / (int)sizeof(T);      // elements per 16-byte chunk
   constexpr int CW = 32 * MI;
-  constexpr int LA = CW + 16;
+  constexpr int LA = CW + (F32 ? 32 : 16);      // (binary32: the two pixels of a pair fall into different halves of the banks)
   constexpr int MAXT = 1320;                    // ((TH<<up)+2) * ((TW<<up)+4) cells for every TW in {16,32,64}, up in {0,1}
-  __shared__ __attribute__((aligned(16))) bf16_t tile[MAXT * 4];
-  __shared__ __attribute__((aligned(16))) bf16_t sW[NT * LA];
+  __shared__ __attribute__((aligned(16))) T tile[MAXT * 4];
+  __shared__ __attribute__((aligned(16))) T sW[NT * LA];
   const int TH = NT >> tw_shift;
   const int IW = TW << up, PW = IW + 4, rows = (TH << up) + 2;
   const int Ht = Hq << up, Wt = Wq << up;
@@ -443,7 +449,7 @@ __global__ __launch_bounds__(NT) void k_thin_wgrad_mfma(const bf16_t* __restrict
     const int n = b / tiles_h;
     const int h0 = ty * TH, w0 = tx * TW;
     // wide slab first (its loads are the long ones): patch pixel p = th*TW + tw -> row p of sW
-    constexpr int CPP = CW / 8;                 // 16-byte chunks per pixel
+    constexpr int CPP = CW / EPC;               // 16-byte chunks per pixel
     uint4 wv[CPP];
 #pragma unroll
     for (int c = 0; c < CPP; ++c) {
@@ -451,7 +457,7 @@ __global__ __launch_bounds__(NT) void k_thin_wgrad_mfma(const bf16_t* __restrict
       const int p = idx / CPP, ch = idx % CPP;
       const int hh = h0 + (p >> tw_shift), ww = w0 + (p & (TW - 1));
       const bool ok = hh < Hq && ww < Wq;
-      wv[c] = *reinterpret_cast<const uint4*>(wide + (((int64_t)n * Hq + min(hh, Hq - 1)) * Wq + min(ww, Wq - 1)) * CW + ch * 8);
+      wv[c] = *reinterpret_cast<const uint4*>(wide + (((int64_t)n * Hq + min(hh, Hq - 1)) * Wq + min(ww, Wq - 1)) * CW + ch * EPC);
       if (!ok) { wv[c].x = 0u; wv[c].y = 0u; wv[c].z = 0u; wv[c].w = 0u; }
     }
     __syncthreads();                            // previous patch fully consumed
@@ -459,9 +465,38 @@ __global__ __launch_bounds__(NT) void k_thin_wgrad_mfma(const bf16_t* __restrict
 #pragma unroll
     for (int c = 0; c < CPP; ++c) {
       const int idx = c * NT + tid;
-      *reinterpret_cast<uint4*>(&sW[(idx / CPP) * LA + (idx % CPP) * 8]) = wv[c];
+      *reinterpret_cast<uint4*>(&sW[(idx / CPP) * LA + (idx % CPP) * EPC]) = wv[c];
     }
     __syncthreads();
+    if constexpr (F32) {
+      const int half = lane >> 5, nl = lane & 31;
+      int boff[2];                              // column k = 32 j + nl of B: k = 16 r + 4 s + ct (columns 48..63 unused: any finite data)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int kq = 32 * j + nl;
+        boff[j] = (min(kq >> 4, 2) * PW + ((kq >> 2) & 3)) * 4 + (kq & 3);
+      }
+      const float* tf = reinterpret_cast<const float*>(tile);
+      const float* wf = reinterpret_cast<const float*>(sW);
+#pragma unroll 4
+      for (int ks = 0; ks < 32; ++ks) {         // this wave's 64 pixels, two per step
+        const int p = wave * 64 + 2 * ks + half;
+        const int th = p >> tw_shift, tw = p & (TW - 1);
+        float a[MI], b[2];
+#pragma unroll
+        for (int i = 0; i < MI; ++i) a[i] = wf[p * LA + i * 32 + nl];
+        const float* q0 = tf + ((th << up) * PW + 1 + (tw << up)) * 4;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const float* q = q0 + boff[j];
+          b[j] = up ? (q[0] + q[4]) + (q[PW * 4] + q[PW * 4 + 4]) : q[0];
+        }
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+      }
+    } else {
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       const int p0 = wave * 64 + ks * 16;       // 16 consecutive pixels of one patch row
@@ -487,6 +522,7 @@ __global__ __launch_bounds__(NT) void k_thin_wgrad_mfma(const bf16_t* __restrict
 #pragma unroll
           for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bfr[j], acc[i][j], 0, 0, 0);
       }
+    }
     }
   }
   // sum the four waves in a fixed order through LDS (reusing the slab), then write [cw][64]
@@ -1250,7 +1286,8 @@ int launch_thin_out_mfma(const void* wide, const float* wcanon, void* wz, const 
 }
 
 bool thin_wgrad_mfma_supported(int ct, int cw, int wq, int dtype) {
-  return dtype == AE_BF16 && ct >= 1 && ct <= 4 && cw % 32 == 0 && cw <= 128 && wq >= 16;
+  if (ct < 1 || ct > 4 || cw % 32 != 0 || wq < 16) return false;
+  return dtype == AE_BF16 ? cw <= 128 : (dtype == AE_F32 && cw <= 64);   // (binary32: the wide slab of a patch is 256 x cw x 4 bytes of LDS)
 }
 
 int thin_wgrad_mfma_blocks(int n, int hq, int wq) {
@@ -1260,8 +1297,8 @@ int thin_wgrad_mfma_blocks(int n, int hq, int wq) {
 // Persistent workgroups actually launched: as many as are resident at once (registers allow
 // three per compute unit for 32 wide channels, two for 64, one beyond), so that every
 // workgroup walks the same number of patches and nobody waits for a second round.
-static int thin_wgrad_mfma_grid(int tiles, int cw) {
-  const int per_cu = cw <= 32 ? 3 : (cw <= 64 ? 2 : 1);
+static int thin_wgrad_mfma_grid(int tiles, int cw, int dtype) {
+  const int per_cu = dtype == AE_F32 ? 1 : (cw <= 32 ? 3 : (cw <= 64 ? 2 : 1));   // (binary32: LDS allows one)
   const int cap = 256 * per_cu;
   return tiles < cap ? tiles : cap;
 }
@@ -1273,20 +1310,25 @@ int64_t thin_wgrad_mfma_workspace_floats(int n, int hq, int wq, int cw) {
 // wide: [n*hq*wq][cw].  mode 0 (first layer): thin = planar layer input [n][ct][hq][wq], up = 0.
 // mode 1 (last layer): thin = planar output gradient [n][ct][hq<<up][wq<<up].
 int launch_thin_wgrad_mfma(const void* thin, const void* wide, float* workspace, float* dw_canonical, int n, int hq,
-                           int wq, int ct, int cw, int mode, int up, hipStream_t s) {
-  if (!thin_wgrad_mfma_supported(ct, cw, wq, AE_BF16) || up < 0 || up > 1 || (mode == 0 && up))
+                           int wq, int ct, int cw, int mode, int up, int dtype, hipStream_t s) {
+  if (!thin_wgrad_mfma_supported(ct, cw, wq, dtype) || up < 0 || up > 1 || (mode == 0 && up))
     return fail(AE_EINVAL, "thin_wgrad_mfma: shape not supported");
+  if (((uintptr_t)wide & 15) != 0) return fail(AE_EINVAL, "thin_wgrad_mfma: the wide tensor must be 16-byte aligned");
   const ThinTile t = thin_tile(n, hq, wq);
-  const int nblk = thin_wgrad_mfma_grid(t.blocks, cw);
+  const int nblk = thin_wgrad_mfma_grid(t.blocks, cw, dtype);
   const int vec = vec_ok(thin, wq << up) ? 1 : 0;
-#define LAUNCH_TWM(MIV)                                                                                         \
-  hipLaunchKernelGGL((k_thin_wgrad_mfma<MIV>), dim3((unsigned)nblk), dim3(NT), 0, s, (const bf16_t*)thin,        \
-                     (const bf16_t*)wide, workspace, hq, wq, ct, up, t.tw, t.shift, t.tiles_w, t.tiles_h, t.blocks, vec)
-  switch (cw / 32) {
-    case 1: LAUNCH_TWM(1); break;
-    case 2: LAUNCH_TWM(2); break;
-    case 3: LAUNCH_TWM(3); break;
-    default: LAUNCH_TWM(4); break;
+#define LAUNCH_TWM(T, MIV)                                                                                      \
+  hipLaunchKernelGGL((k_thin_wgrad_mfma<T, MIV>), dim3((unsigned)nblk), dim3(NT), 0, s, (const T*)thin,          \
+                     (const T*)wide, workspace, hq, wq, ct, up, t.tw, t.shift, t.tiles_w, t.tiles_h, t.blocks, vec)
+  if (dtype == AE_F32) {
+    if (cw == 32) LAUNCH_TWM(float, 1); else LAUNCH_TWM(float, 2);
+  } else {
+    switch (cw / 32) {
+      case 1: LAUNCH_TWM(bf16_t, 1); break;
+      case 2: LAUNCH_TWM(bf16_t, 2); break;
+      case 3: LAUNCH_TWM(bf16_t, 3); break;
+      default: LAUNCH_TWM(bf16_t, 4); break;
+    }
   }
 #undef LAUNCH_TWM
   AE_TRY(launch_status("thin_wgrad_mfma"));

@@ -245,7 +245,7 @@ int launch_thin_out_mfma(const void* wide, const float* wcanon, void* wz, const 
 bool thin_wgrad_mfma_supported(int ct, int cw, int wq, int dtype);
 int64_t thin_wgrad_mfma_workspace_floats(int n, int hq, int wq, int cw);
 int launch_thin_wgrad_mfma(const void* thin, const void* wide, float* workspace, float* dw_canonical, int n, int hq,
-                           int wq, int ct, int cw, int mode, int up, hipStream_t s);
+                           int wq, int ct, int cw, int mode, int up, int dtype, hipStream_t s);
 int64_t thin_wgrad_workspace_floats(int64_t q_pixels, int ct, int cw);
 int launch_thin_wgrad(const void* thin, const void* wide, float* workspace, float* dw_canonical, int n, int hq, int wq,
                       int ct, int cw, int mode, int up, int dtype, hipStream_t s);

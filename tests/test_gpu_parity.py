@@ -140,6 +140,8 @@ def test_thin_layers_on_ragged_images_binary32(ae, case):
     names = {t["name"].split(".", 1)[1] for t in m.model_timing_read() if t["launches"]}
     m.close()
     assert {"fwd.conv_thin_in_mfma", "fwd.conv_thin_out_mfma", "bwd.dgrad_thin_mfma"} <= names, sorted(names)
+    if case != 1:   # (images at least 16 wide: the thin weight gradients as well)
+        assert "bwd.wgrad_thin_mfma" in names and "bwd.wgrad_thin" not in names, sorted(names)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
